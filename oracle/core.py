@@ -1,0 +1,487 @@
+"""CPU ORACLE -- TEST INFRASTRUCTURE, NOT PART OF THE PRODUCT.  See the package docstring."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from typing import Dict, Iterable, List, Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "liboracle.so")
+_SRC_PATH = os.path.join(_HERE, "ckks_oracle.cpp")
+_lib = None
+
+u64p = C.POINTER(C.c_uint64)
+
+
+def build(force: bool = False) -> str:
+    """Compile the C++ core with g++ (plain -O2, OpenMP over independent limbs)."""
+    if force or not os.path.exists(_LIB_PATH) or os.path.getmtime(_LIB_PATH) < os.path.getmtime(_SRC_PATH):
+        subprocess.check_call(["g++", "-O2", "-fopenmp", "-shared", "-fPIC", "-o", _LIB_PATH, _SRC_PATH])
+    return _LIB_PATH
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = C.CDLL(_LIB_PATH)
+        _lib.orc_create.restype = C.c_void_p
+        _lib.orc_live_digits.restype = C.c_int
+    return _lib
+
+
+def _u64(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.uint64)
+
+
+def _p(a: np.ndarray):
+    return a.ctypes.data_as(C.c_void_p)
+
+
+def round_half_away(x: np.ndarray) -> np.ndarray:
+    return np.where(x >= 0, np.floor(x + 0.5), np.ceil(x - 0.5))
+
+
+# odd degree-7 polynomial with p(0)=0, p(+-1)=+-1, p'(+-1)=p''(+-1)=p'''(+-1)=0
+ACT_COEFFS = (35.0 / 16.0, -35.0 / 16.0, 21.0 / 16.0, -5.0 / 16.0)
+
+
+def activation_reference(x: np.ndarray) -> np.ndarray:
+    c1, c3, c5, c7 = ACT_COEFFS
+    return c1 * x + c3 * x**3 + c5 * x**5 + c7 * x**7
+
+
+def conv2d_reference(images: np.ndarray, weights: np.ndarray) -> np.ndarray:
+    """float64 cross-correlation, 3x3, stride 1, zero padding 1.
+    images [B, C_in, H, W], weights [C_out, C_in, 3, 3] -> [B, C_out, H, W]:
+    out[b,o,y,x] = sum_c sum_{dy,dx} weights[o,c,dy+1,dx+1] * images[b,c,y+dy,x+dx]."""
+    B, Ci, H, W = images.shape
+    Co = weights.shape[0]
+    padded = np.zeros((B, Ci, H + 2, W + 2), dtype=np.float64)
+    padded[:, :, 1:H + 1, 1:W + 1] = images
+    out = np.zeros((B, Co, H, W), dtype=np.float64)
+    for o in range(Co):
+        for c in range(Ci):
+            for dy in (-1, 0, 1):
+                for dx in (-1, 0, 1):
+                    out[:, o] += weights[o, c, dy + 1, dx + 1] * padded[:, c, 1 + dy:1 + dy + H, 1 + dx:1 + dx + W]
+    return out
+
+
+class Oracle:
+    """One RNS-CKKS context (ring degree, modulus chain, special primes, digit count)."""
+
+    def __init__(self, params):
+        lib = _load()
+        self.lib = lib
+        self.log_n = int(params.log_n)
+        self.N = 1 << self.log_n
+        self.n = self.N // 2
+        self.num_q = int(params.num_q)
+        self.num_p = int(params.num_p)
+        self.dnum = int(params.dnum)
+        self.alpha = -(-self.num_q // self.dnum) if self.dnum else 0
+        self.moduli = [int(q) for q in params.moduli]
+        self.psi = [int(x) for x in params.psi]
+        self.M = self.num_q + self.num_p
+        mods = np.array(self.moduli, dtype=np.uint64)
+        psis = np.array(self.psi, dtype=np.uint64)
+        self.h = C.c_void_p(lib.orc_create(self.log_n, self.num_q, self.num_p, self.dnum, _p(mods), _p(psis)))
+        if not self.h:
+            raise ValueError("psi is not a primitive 2N-th root of unity for some modulus")
+
+    def __del__(self):
+        try:
+            self.lib.orc_destroy(self.h)
+        except Exception:
+            pass
+
+    # ----------------------------------------------------------------------------- NTT
+    def ntt_fwd(self, a, mod_idx: int) -> np.ndarray:
+        a = _u64(a).copy()
+        self.lib.orc_ntt_fwd(self.h, int(mod_idx), _p(a))
+        return a
+
+    def ntt_inv(self, a, mod_idx: int) -> np.ndarray:
+        a = _u64(a).copy()
+        self.lib.orc_ntt_inv(self.h, int(mod_idx), _p(a))
+        return a
+
+    def ntt_definition(self, a, mod_idx: int) -> np.ndarray:
+        a = _u64(a)
+        out = np.empty_like(a)
+        self.lib.orc_ntt_definition(self.h, int(mod_idx), _p(a), _p(out))
+        return out
+
+    def ntt_many(self, polys, mod_idx: Sequence[int], inverse: bool = False) -> np.ndarray:
+        """polys [..., n_limbs, N]; limb t uses modulus mod_idx[t].  Returns a new array."""
+        a = _u64(polys).copy()
+        n_limbs = len(mod_idx)
+        assert a.shape[-2] == n_limbs and a.shape[-1] == self.N
+        idx = np.array(mod_idx, dtype=np.int32)
+        batch = a.size // (n_limbs * self.N)
+        self.lib.orc_ntt_many(self.h, _p(a), _p(idx), n_limbs, batch, int(bool(inverse)))
+        return a
+
+    def schoolbook(self, q: int, a, b) -> np.ndarray:
+        a, b = _u64(a), _u64(b)
+        out = np.empty_like(a)
+        self.lib.orc_negacyclic_schoolbook(C.c_uint64(q), len(a), _p(a), _p(b), _p(out))
+        return out
+
+    # -------------------------------------------------------------------- automorphism
+    def galois(self, offset: int) -> int:
+        """Galois element of a left rotation by `offset` slots: 5^offset mod 2N."""
+        return pow(5, offset % self.n, 2 * self.N)
+
+    def automorph_coeff(self, a, mod_idx: int, g: int) -> np.ndarray:
+        a = _u64(a)
+        out = np.empty_like(a)
+        self.lib.orc_automorph_coeff(self.h, int(mod_idx), C.c_uint64(g), _p(a), _p(out))
+        return out
+
+    def automorph_ntt(self, a, g: int) -> np.ndarray:
+        """a [..., N] in NTT form; the same gather on every limb."""
+        a = _u64(a)
+        out = np.empty_like(a)
+        flat_in, flat_out = a.reshape(-1, self.N), out.reshape(-1, self.N)
+        for i in range(flat_in.shape[0]):
+            self.lib.orc_automorph_ntt(self.h, C.c_uint64(g), _p(flat_in[i]), _p(flat_out[i]))
+        return out
+
+    # -------------------------------------------------------------------- key switching
+    def live_digits(self, level: int) -> int:
+        return (level + self.alpha) // self.alpha
+
+    def ext_moduli_idx(self, level: int) -> List[int]:
+        return list(range(level + 1)) + list(range(self.num_q, self.M))
+
+    def modup(self, c, level: int) -> np.ndarray:
+        c = _u64(c)
+        assert c.shape == (level + 1, self.N)
+        out = np.empty((self.live_digits(level), level + 1 + self.num_p, self.N), dtype=np.uint64)
+        self.lib.orc_modup(self.h, level, _p(c), _p(out))
+        return out
+
+    def key_inner(self, digits, key, level: int) -> np.ndarray:
+        digits, key = _u64(digits), _u64(key)
+        assert key.shape == (self.dnum, 2, self.M, self.N)
+        out = np.empty((2, level + 1 + self.num_p, self.N), dtype=np.uint64)
+        self.lib.orc_key_inner(self.h, level, _p(digits), _p(key), _p(out))
+        return out
+
+    def moddown(self, v, level: int) -> np.ndarray:
+        v = _u64(v)
+        assert v.shape == (level + 1 + self.num_p, self.N)
+        out = np.empty((level + 1, self.N), dtype=np.uint64)
+        self.lib.orc_moddown(self.h, level, _p(v), _p(out))
+        return out
+
+    def keyswitch(self, c, key, level: int) -> np.ndarray:
+        c, key = _u64(c), _u64(key)
+        assert c.shape == (level + 1, self.N) and key.shape == (self.dnum, 2, self.M, self.N)
+        out = np.empty((2, level + 1, self.N), dtype=np.uint64)
+        self.lib.orc_keyswitch(self.h, level, _p(c), _p(key), _p(out))
+        return out
+
+    def rotate(self, ct, level: int, offset: int, key, hoisted: bool, digits=None) -> np.ndarray:
+        """Rot(ct, offset): slot i of the result holds slot (i+offset) mod n of the input."""
+        ct = _u64(ct)
+        assert ct.shape == (2, level + 1, self.N)
+        if offset % self.n == 0:
+            return ct.copy()
+        key = _u64(key)
+        g = self.galois(offset)
+        out = np.empty_like(ct)
+        if hoisted:
+            if digits is None:
+                digits = self.modup(ct[1], level)
+            digits = _u64(digits)
+            self.lib.orc_rotate_hoisted(self.h, level, C.c_uint64(g), _p(ct), _p(digits), _p(key), _p(out))
+        else:
+            self.lib.orc_rotate_unhoisted(self.h, level, C.c_uint64(g), _p(ct), _p(key), _p(out))
+        return out
+
+    def rotate_many(self, ct, level: int, offsets: Sequence[int], keys: Sequence, hoisted: bool) -> List[np.ndarray]:
+        digits = self.modup(_u64(ct)[1], level) if hoisted else None
+        return [self.rotate(ct, level, r, k, hoisted, digits) for r, k in zip(offsets, keys)]
+
+    # ------------------------------------------------------------------------ pointwise
+    def ptct_mac(self, pts: Sequence[np.ndarray], cts: Sequence[np.ndarray], level: int,
+                 acc: Optional[np.ndarray] = None) -> np.ndarray:
+        """sum_k pt_k (.) ct_k  (+ acc): Eq. 11 with the channel sum folded into the same sum."""
+        assert len(pts) == len(cts)
+        pts = [_u64(p) for p in pts]
+        cts = [_u64(c) for c in cts]
+        for p_, c_ in zip(pts, cts):
+            assert p_.shape == (level + 1, self.N) and c_.shape == (2, level + 1, self.N)
+        accumulate = acc is not None
+        out = _u64(acc).copy() if accumulate else np.empty((2, level + 1, self.N), dtype=np.uint64)
+        n = len(pts)
+        pa = (C.c_void_p * n)(*[p_.ctypes.data for p_ in pts])
+        ca = (C.c_void_p * n)(*[c_.ctypes.data for c_ in cts])
+        self.lib.orc_ptct_mac(self.h, level, n, pa, ca, _p(out), int(accumulate))
+        return out
+
+    def scalar_residues(self, value: int, level: int) -> np.ndarray:
+        """Residues of a (signed) integer scalar modulo q_0..q_level."""
+        return np.array([int(value) % self.moduli[i] for i in range(level + 1)], dtype=np.uint64)
+
+    def scalar_mul(self, poly, scalar_res, level: int) -> np.ndarray:
+        """poly [n_comp, level+1, N] (or [level+1, N]) times an integer scalar given by residues."""
+        poly = _u64(poly)
+        n_comp = poly.size // ((level + 1) * self.N)
+        out = np.empty_like(poly)
+        self.lib.orc_scalar_mul(self.h, level, n_comp, _p(poly), _p(_u64(scalar_res)), _p(out))
+        return out
+
+    def add(self, a, b, level: int) -> np.ndarray:
+        a, b = _u64(a), _u64(b)
+        assert a.shape == b.shape
+        n_comp = a.size // ((level + 1) * self.N)
+        out = np.empty_like(a)
+        self.lib.orc_add(self.h, level, n_comp, _p(a), _p(b), _p(out))
+        return out
+
+    @staticmethod
+    def drop_to_level(ct, level: int) -> np.ndarray:
+        """Forget limbs above `level` (RNS: lower levels are a prefix of the limbs)."""
+        return np.ascontiguousarray(_u64(ct)[:, :level + 1, :])
+
+    def rescale(self, ct, level: int) -> np.ndarray:
+        ct = _u64(ct)
+        assert ct.shape == (2, level + 1, self.N) and level >= 1
+        out = np.empty((2, level, self.N), dtype=np.uint64)
+        self.lib.orc_rescale(self.h, level, _p(ct), _p(out))
+        return out
+
+    def ctct_mul_relin(self, a, b, rlk, level: int) -> np.ndarray:
+        a, b, rlk = _u64(a), _u64(b), _u64(rlk)
+        assert a.shape == b.shape == (2, level + 1, self.N)
+        out = np.empty_like(a)
+        self.lib.orc_ctct_mul_relin(self.h, level, _p(a), _p(b), _p(rlk), _p(out))
+        return out
+
+    # ------------------------------------------------------------------- encode / decode
+    def _slot_index(self) -> np.ndarray:
+        """k_j with zeta^(2 k_j + 1) = zeta^(5^j), j < n."""
+        idx = np.empty(self.n, dtype=np.int64)
+        e = 1
+        for j in range(self.n):
+            idx[j] = (e - 1) // 2
+            e = e * 5 % (2 * self.N)
+        return idx
+
+    def encode(self, z: np.ndarray, scale: float) -> np.ndarray:
+        """Real slot vector z[n] -> int64 coefficients m with m(zeta^(5^j)) ~ scale * z_j.
+        The values at all N odd powers of zeta (slot values and their conjugates) are turned into
+        coefficients by one FFT: m_i zeta^i = (1/N) sum_k v_k exp(-2 pi i ik/N)."""
+        z = np.asarray(z, dtype=np.float64)
+        assert z.shape == (self.n,)
+        idx = self._slot_index()
+        v = np.zeros(self.N, dtype=np.complex128)
+        v[idx] = z
+        v[self.N - 1 - idx] = z  # exponent -(2k+1) = 2(N-1-k)+1 mod 2N carries the conjugate
+        i = np.arange(self.N)
+        twist = np.exp(-1j * np.pi * i / self.N)
+        m = (np.fft.fft(v) / self.N * twist).real * scale
+        return round_half_away(m).astype(np.int64)
+
+    def decode(self, coeffs: np.ndarray, scale: float) -> np.ndarray:
+        """Coefficients (float64 or integer) -> real parts of the n slots, divided by scale."""
+        m = np.asarray(coeffs, dtype=np.float64)
+        i = np.arange(self.N)
+        v = np.fft.ifft(m * np.exp(1j * np.pi * i / self.N)) * self.N
+        return v[self._slot_index()].real / scale
+
+    def embed_definition(self, coeffs: np.ndarray) -> np.ndarray:
+        """O(N^2) canonical embedding: slot j = sum_i m_i zeta^(5^j i).  For pinning only."""
+        m = np.asarray(coeffs, dtype=np.float64)
+        out = np.empty(self.n, dtype=np.complex128)
+        e = 1
+        i = np.arange(self.N)
+        for j in range(self.n):
+            out[j] = np.sum(m * np.exp(1j * np.pi * ((e * i) % (2 * self.N)) / self.N))
+            e = e * 5 % (2 * self.N)
+        return out
+
+    def lift_ntt(self, coeffs: np.ndarray, mod_idx: Sequence[int]) -> np.ndarray:
+        coeffs = np.ascontiguousarray(coeffs, dtype=np.int64)
+        idx = np.array(mod_idx, dtype=np.int32)
+        out = np.empty((len(idx), self.N), dtype=np.uint64)
+        self.lib.orc_lift_ntt(self.h, _p(coeffs), _p(idx), len(idx), _p(out))
+        return out
+
+    def encode_ntt(self, z: np.ndarray, scale: float, level: int) -> np.ndarray:
+        """Plaintext polynomial [level+1][N] in NTT form."""
+        return self.lift_ntt(self.encode(z, scale), list(range(level + 1)))
+
+    # --------------------------------------------------------------------------- client
+    def gen_secret(self, seed: int) -> Tuple[np.ndarray, np.ndarray]:
+        """Ternary secret: (int64 coefficients, NTT form over all num_q+num_p moduli)."""
+        s8 = np.empty(self.N, dtype=np.int8)
+        self.lib.orc_sample_ternary(C.c_uint64(seed), self.N, _p(s8))
+        s = s8.astype(np.int64)
+        return s, self.lift_ntt(s, list(range(self.M)))
+
+    def _gen_switch_key(self, s_ntt, sp_ntt, seed: int) -> np.ndarray:
+        key = np.empty((self.dnum, 2, self.M, self.N), dtype=np.uint64)
+        self.lib.orc_gen_switch_key(self.h, _p(_u64(s_ntt)), _p(_u64(sp_ntt)), C.c_uint64(seed), _p(key))
+        return key
+
+    def gen_rotation_key(self, s: np.ndarray, s_ntt: np.ndarray, offset: int, seed: int) -> np.ndarray:
+        """Key switching from sigma_g(s) to s, g = 5^offset."""
+        g = self.galois(offset)
+        # sigma_g on the small signed coefficients: index i -> i*g mod 2N with the negacyclic sign
+        sp = np.zeros(self.N, dtype=np.int64)
+        e = (np.arange(self.N, dtype=np.int64) * g) % (2 * self.N)
+        sp[e % self.N] = np.where(e < self.N, s, -s)
+        return self._gen_switch_key(s_ntt, self.lift_ntt(sp, list(range(self.M))), seed)
+
+    def mul(self, a, b, mod_idx: Sequence[int]) -> np.ndarray:
+        """a (.) b, limb t modulo moduli[mod_idx[t]]; a, b [len(mod_idx)][N]."""
+        a, b = _u64(a), _u64(b)
+        idx = np.array(mod_idx, dtype=np.int32)
+        assert a.shape == b.shape == (len(idx), self.N)
+        out = np.empty_like(a)
+        self.lib.orc_mul(self.h, _p(idx), len(idx), _p(a), _p(b), _p(out))
+        return out
+
+    def gen_relin_key(self, s_ntt: np.ndarray, seed: int) -> np.ndarray:
+        """Key switching from s^2 to s."""
+        s2 = self.mul(s_ntt, s_ntt, list(range(self.M)))
+        return self._gen_switch_key(s_ntt, s2, seed)
+
+    def encrypt_coeffs(self, m: np.ndarray, level: int, s_ntt: np.ndarray, seed: int) -> np.ndarray:
+        ct = np.empty((2, level + 1, self.N), dtype=np.uint64)
+        m = np.ascontiguousarray(m, dtype=np.int64)
+        self.lib.orc_encrypt(self.h, level, _p(m), _p(_u64(s_ntt)), C.c_uint64(seed), _p(ct))
+        return ct
+
+    def encrypt(self, z: np.ndarray, scale: float, level: int, s_ntt: np.ndarray, seed: int) -> np.ndarray:
+        return self.encrypt_coeffs(self.encode(z, scale), level, s_ntt, seed)
+
+    def decrypt_coeffs(self, ct, level: int, s_ntt: np.ndarray) -> np.ndarray:
+        ct = _u64(ct)
+        assert ct.shape == (2, level + 1, self.N)
+        out = np.empty(self.N, dtype=np.float64)
+        self.lib.orc_decrypt(self.h, level, _p(ct), _p(_u64(s_ntt)), _p(out))
+        return out
+
+    def decrypt(self, ct, level: int, s_ntt: np.ndarray, scale: float) -> np.ndarray:
+        return self.decode(self.decrypt_coeffs(ct, level, s_ntt), scale)
+
+    # ------------------------------------------------------------- batched convolution
+    def pack_channel(self, images: np.ndarray, channel: int) -> np.ndarray:
+        """Channel-by-channel packing (Eqs. 3 and 5): image j's flattened channel occupies slots
+        [j*m, (j+1)*m), m = H*W; needs m*b <= n (Eq. 4).  Unused slots are zero."""
+        B, _, H, W = images.shape
+        m = H * W
+        if m * B > self.n:
+            raise ValueError("slot constraint m*b <= n violated")
+        z = np.zeros(self.n, dtype=np.float64)
+        z[:m * B] = images[:, channel].reshape(B, m).reshape(-1)
+        return z
+
+    def unpack_channel(self, z: np.ndarray, batch: int, height: int, width: int) -> np.ndarray:
+        return np.asarray(z[:batch * height * width]).reshape(batch, height, width)
+
+    def tap_masks(self, height: int, width: int, batch: int) -> np.ndarray:
+        """[9][n] 0/1 vectors, tap (dy,dx) in row-major order: 1 where the neighbour (y+dy, x+dx)
+        lies inside the same image.  Replicated over the batch segments (Eq. 7)."""
+        masks = np.zeros((9, self.n), dtype=np.float64)
+        m = height * width
+        y, x = np.divmod(np.arange(m), width)
+        t = 0
+        for dy in (-1, 0, 1):
+            for dx in (-1, 0, 1):
+                ok = ((y + dy >= 0) & (y + dy < height) & (x + dx >= 0) & (x + dx < width)).astype(np.float64)
+                masks[t, :m * batch] = np.tile(ok, batch)
+                t += 1
+        return masks
+
+    def conv_operands(self, weights: np.ndarray, height: int, width: int, batch: int, level: int,
+                      delta_m: float, delta_w: float) -> Tuple[np.ndarray, np.ndarray]:
+        """The two factors of the weight plaintexts pt[o,c,tap] = w_int[o,c,tap] * M_tap:
+        M [9][level+1][N] (NTT form, masks encoded at delta_m) and the integer weights
+        w_int [C_out][C_in][9] = round(w * delta_w) as int64."""
+        masks = self.tap_masks(height, width, batch)
+        M = np.stack([self.encode_ntt(masks[t], delta_m, level) for t in range(9)])
+        w_int = round_half_away(np.asarray(weights, dtype=np.float64).reshape(weights.shape[0], weights.shape[1], 9) * delta_w).astype(np.int64)
+        return M, w_int
+
+    def he_conv(self, cts: Sequence[np.ndarray], level: int, width: int, rot_keys: Dict[int, np.ndarray],
+                M: np.ndarray, w_int: np.ndarray, out_channels: Optional[Iterable[int]] = None,
+                hoisted: bool = True) -> Dict[int, np.ndarray]:
+        """Batched 3x3 convolution layer on channel-packed ciphertexts:
+        out_o = Rescale( sum_c sum_tap pt[o,c,tap] (.) Rot(ct_c, dy*W+dx) )   (Eqs. 10-11).
+        rot_keys maps the slot offset to its rotation key.  Returns {o: ct at level-1}."""
+        C_in = len(cts)
+        offsets = [dy * width + dx for dy in (-1, 0, 1) for dx in (-1, 0, 1)]
+        aligned: List[List[np.ndarray]] = []
+        for c in range(C_in):
+            digits = self.modup(_u64(cts[c])[1], level) if hoisted else None
+            row = []
+            for off in offsets:
+                if off == 0:
+                    row.append(_u64(cts[c]))
+                else:
+                    row.append(self.rotate(cts[c], level, off, rot_keys[off], hoisted, digits))
+            aligned.append(row)
+        outs = {}
+        chans = range(w_int.shape[0]) if out_channels is None else out_channels
+        for o in chans:
+            pts, terms = [], []
+            for c in range(C_in):
+                for t in range(9):
+                    pts.append(self.scalar_mul(M[t], self.scalar_residues(int(w_int[o, c, t]), level), level))
+                    terms.append(aligned[c][t])
+            acc = self.ptct_mac(pts, terms, level)
+            outs[o] = self.rescale(acc, level)
+        return outs
+
+    # ----------------------------------------------------------------------- activation
+    def act_schedule(self, level: int, scale: float) -> dict:
+        """Levels, scales and integer scalars of the degree-7 activation evaluated on a
+        ciphertext at (level, scale) with four ciphertext products:
+            x2 = x*x, x3 = x2*x, x4 = x2*x2   (each rescaled once)
+            B  = Rescale(k5*x + k7*x3)
+            y  = Rescale((k1*x + k3*x3) + x4*B)
+        The integer scalars fold the polynomial coefficients and equalise the scales."""
+        q = self.moduli
+        c1, c3, c5, c7 = ACT_COEFFS
+        s1 = float(scale)
+        s2 = s1 * s1 / q[level]            # x2 at level-1
+        s3 = s2 * s1 / q[level - 1]        # x3 at level-2
+        s4 = s2 * s2 / q[level - 1]        # x4 at level-2
+        tB = s3 * q[level - 2]             # B before its rescale (level-2)
+        k5 = int(round_half_away(np.float64(c5 * tB / s1)))
+        k7 = int(round_half_away(np.float64(c7 * tB / s3)))
+        sB = tB / q[level - 2]             # B at level-3
+        tY = s4 * sB                       # y before its rescale (level-3)
+        k1 = int(round_half_away(np.float64(c1 * tY / s1)))
+        k3 = int(round_half_away(np.float64(c3 * tY / s3)))
+        return dict(k=(k1, k3, k5, k7), out_level=level - 4, out_scale=tY / q[level - 3])
+
+    def poly_activation(self, x, level: int, k: Sequence[int], rlk) -> np.ndarray:
+        """Degree-7 odd polynomial with integer scalars k = (k1, k3, k5, k7) as produced by
+        act_schedule; input at `level`, output at level-4."""
+        k1, k3, k5, k7 = [int(v) for v in k]
+        x = _u64(x)
+        x2 = self.rescale(self.ctct_mul_relin(x, x, rlk, level), level)                    # level-1
+        xd1 = self.drop_to_level(x, level - 1)
+        x3 = self.rescale(self.ctct_mul_relin(x2, xd1, rlk, level - 1), level - 1)          # level-2
+        x4 = self.rescale(self.ctct_mul_relin(x2, x2, rlk, level - 1), level - 1)           # level-2
+        xd2 = self.drop_to_level(x, level - 2)
+        l2 = level - 2
+        Bp = self.add(self.scalar_mul(xd2, self.scalar_residues(k5, l2), l2),
+                      self.scalar_mul(x3, self.scalar_residues(k7, l2), l2), l2)
+        B = self.rescale(Bp, l2)                                                            # level-3
+        l3 = level - 3
+        A = self.add(self.scalar_mul(self.drop_to_level(x, l3), self.scalar_residues(k1, l3), l3),
+                     self.scalar_mul(self.drop_to_level(x3, l3), self.scalar_residues(k3, l3), l3), l3)
+        prod = self.ctct_mul_relin(self.drop_to_level(x4, l3), B, rlk, l3)
+        return self.rescale(self.add(A, prod, l3), l3)                                      # level-4

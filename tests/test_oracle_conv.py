@@ -1,0 +1,169 @@
+"""Pins for the oracle's client side and the batched convolution: the canonical embedding by
+its O(N^2) definition, the float64 convolution against scipy, decrypted HE convolutions against
+the float64 convolution, and special cases that collapse to simpler operations."""
+import numpy as np
+import pytest
+from scipy.signal import correlate2d
+
+from oracle import Oracle, conv2d_reference, activation_reference, ACT_COEFFS
+from workloads import CONFIGS, make_params, image_batch, conv_weights, conv_tap_offsets
+
+
+def test_encode_decode_against_embedding_definition():
+    o = Oracle(make_params(8, 1, 0, 1))
+    rng = np.random.default_rng(0)
+    z = rng.uniform(-1, 1, o.n)
+    m = o.encode(z, 2.0 ** 30)
+    slots = o.embed_definition(m) / 2.0 ** 30
+    assert np.abs(slots.real - z).max() < 1e-6 and np.abs(slots.imag).max() < 1e-6
+    assert np.abs(o.decode(m, 2.0 ** 30) - slots.real).max() < 1e-9
+    # a constant vector encodes to a constant polynomial, the slot index e_0 alone to a known one
+    assert o.encode(np.full(o.n, 0.75), 2.0 ** 20).tolist() == [int(0.75 * 2 ** 20)] + [0] * (o.N - 1)
+
+
+@pytest.mark.parametrize("log_n", [5, 12, 16])
+def test_encode_decode_round_trip(log_n):
+    o = Oracle(make_params(log_n, 1, 0, 1))
+    z = np.random.default_rng(1).uniform(-1, 1, o.n)
+    assert np.abs(o.decode(o.encode(z, 2.0 ** 40), 2.0 ** 40) - z).max() < 2.0 ** -30
+
+
+def test_product_of_encodings_is_slotwise_product():
+    p = make_params(6, 2, 0, 1)
+    o = Oracle(p)
+    rng = np.random.default_rng(2)
+    za, zb = rng.uniform(-1, 1, o.n), rng.uniform(-1, 1, o.n)
+    sc = 2.0 ** 20
+    q = p.moduli[0]
+    a = np.array([int(v) % q for v in o.encode(za, sc)], dtype=np.uint64)
+    b = np.array([int(v) % q for v in o.encode(zb, sc)], dtype=np.uint64)
+    c = o.schoolbook(q, a, b)
+    cc = np.array([int(v) - q if int(v) > q // 2 else int(v) for v in c], dtype=np.float64)
+    assert np.abs(o.decode(cc, sc * sc) - za * zb).max() < 1e-4
+
+
+def test_rounding_is_half_away_from_zero():
+    from oracle.core import round_half_away
+    assert round_half_away(np.array([0.5, -0.5, 1.5, -1.5, 2.4, -2.6])).tolist() == [1, -1, 2, -2, 2, -3]
+
+
+def test_encrypt_decrypt(cfg1_params):
+    o = Oracle(cfg1_params)
+    s, s_ntt = o.gen_secret(1)
+    z = np.random.default_rng(3).uniform(-1, 1, o.n)
+    for level in (3, 1, 0):
+        ct = o.encrypt(z, 2.0 ** 40, level, s_ntt, 2 + level)
+        assert np.abs(o.decrypt(ct, level, s_ntt, 2.0 ** 40) - z).max() < 1e-8
+    _, other = o.gen_secret(99)
+    assert np.abs(o.decrypt(ct, 0, other, 2.0 ** 40) - z).max() > 1.0
+
+
+def test_float_conv_matches_scipy():
+    rng = np.random.default_rng(4)
+    img = rng.uniform(-1, 1, (3, 4, 6, 5))
+    w = rng.normal(0, 0.3, (2, 4, 3, 3))
+    got = conv2d_reference(img, w)
+    for b in range(3):
+        for o_ in range(2):
+            want = sum(correlate2d(img[b, c], w[o_, c], mode="same", boundary="fill", fillvalue=0) for c in range(4))
+            assert np.abs(got[b, o_] - want).max() < 1e-12
+
+
+def test_pack_and_masks():
+    o = Oracle(make_params(8, 1, 0, 1))
+    img = np.arange(2 * 1 * 4 * 4, dtype=np.float64).reshape(2, 1, 4, 4)
+    z = o.pack_channel(img, 0)
+    assert z[:32].tolist() == list(range(32)) and not z[32:].any()
+    with pytest.raises(ValueError):
+        o.pack_channel(np.zeros((9, 1, 4, 4)), 0)  # 9*16 > 128 slots
+    masks = o.tap_masks(4, 4, 2)
+    assert masks[4, :32].all() and not masks[:, 32:].any()          # centre tap: all ones
+    top_left = masks[0, :16].reshape(4, 4)                          # tap (-1,-1)
+    assert not top_left[0].any() and not top_left[:, 0].any() and top_left[1:, 1:].all()
+    assert np.array_equal(masks[0, :16], masks[0, 16:32])            # replicated over the batch
+    # masked roll == zero-padded shift, including across image boundaries
+    offs = conv_tap_offsets(4)
+    for t, (dy, dx) in enumerate([(a, b) for a in (-1, 0, 1) for b in (-1, 0, 1)]):
+        shifted = np.zeros_like(img)
+        for y in range(4):
+            for x in range(4):
+                if 0 <= y + dy < 4 and 0 <= x + dx < 4:
+                    shifted[:, :, y, x] = img[:, :, y + dy, x + dx]
+        assert np.array_equal((np.roll(z, -offs[t]) * masks[t])[:32], shifted.reshape(-1))
+
+
+def _conv_setup(name, seed_base, level=None):
+    wl = CONFIGS[name]
+    p = wl.params()
+    o = Oracle(p)
+    level = p.num_q - 1 if level is None else level
+    s, s_ntt = o.gen_secret(seed_base)
+    img = image_batch(wl.batch, wl.c_in, wl.height, wl.width)
+    w = conv_weights(wl.c_out, wl.c_in, dist="uniform" if wl.c_in == 1 else "he_normal")
+    scale = 2.0 ** 40
+    cts = [o.encrypt(o.pack_channel(img, c), scale, level, s_ntt, seed_base + 10 + c) for c in range(wl.c_in)]
+    keys = {off: o.gen_rotation_key(s, s_ntt, off, seed_base + 100 + i)
+            for i, off in enumerate(conv_tap_offsets(wl.width)) if off != 0}
+    return wl, p, o, level, s, s_ntt, img, w, scale, cts, keys
+
+
+@pytest.mark.parametrize("name", ["cfg1_single_conv", "small_conv"])
+def test_he_conv_decrypts_to_float_conv(name):
+    wl, p, o, level, s, s_ntt, img, w, scale, cts, keys = _conv_setup(name, 1000)
+    delta_m = 2.0 ** 28
+    delta_w = p.moduli[level] / delta_m           # so that the rescale restores the input scale
+    M, w_int = o.conv_operands(w, wl.height, wl.width, wl.batch, level, delta_m, delta_w)
+    outs = o.he_conv(cts, level, wl.width, keys, M, w_int)
+    want = conv2d_reference(img, w)
+    for oc, ct in outs.items():
+        got = o.unpack_channel(o.decrypt(ct, level - 1, s_ntt, scale), wl.batch, wl.height, wl.width)
+        assert np.abs(got - want[:, oc]).max() < 1e-4
+    # unused slots stay (almost) zero
+    z = o.decrypt(outs[0], level - 1, s_ntt, scale)
+    assert np.abs(z[wl.batch * wl.height * wl.width:]).max() < 1e-4 if wl.batch * wl.height * wl.width < o.n else True
+
+
+def test_he_conv_centre_only_kernel_is_scalar_multiple():
+    wl, p, o, level, s, s_ntt, img, w, scale, cts, keys = _conv_setup("cfg1_single_conv", 2000)
+    w = np.zeros_like(w)
+    w[0, 0, 1, 1] = 0.375
+    delta_m = 2.0 ** 28
+    M, w_int = o.conv_operands(w, wl.height, wl.width, wl.batch, level, delta_m, p.moduli[level] / delta_m)
+    out = o.he_conv(cts, level, wl.width, keys, M, w_int)[0]
+    got = o.decrypt(out, level - 1, s_ntt, scale)
+    assert np.abs(got - 0.375 * o.pack_channel(img, 0)).max() < 1e-5
+
+
+def test_he_conv_unhoisted_schedule_agrees_after_decryption():
+    wl, p, o, level, s, s_ntt, img, w, scale, cts, keys = _conv_setup("cfg1_single_conv", 3000)
+    delta_m = 2.0 ** 28
+    M, w_int = o.conv_operands(w, wl.height, wl.width, wl.batch, level, delta_m, p.moduli[level] / delta_m)
+    a = o.he_conv(cts, level, wl.width, keys, M, w_int, hoisted=True)[0]
+    b = o.he_conv(cts, level, wl.width, keys, M, w_int, hoisted=False)[0]
+    assert not np.array_equal(a, b)
+    assert np.abs(o.decrypt(a, level - 1, s_ntt, scale) - o.decrypt(b, level - 1, s_ntt, scale)).max() < 1e-5
+
+
+def test_activation_polynomial_pins():
+    assert activation_reference(np.array([0.0, 1.0, -1.0])).tolist() == [0.0, 1.0, -1.0]
+    # p'(x) = 35/16 (1-x^2)^3: flat at +-1
+    h = 1e-4
+    assert abs(activation_reference(np.array([1 - h]))[0] - 1) < 1e-10
+    assert abs(sum(ACT_COEFFS) - 1) < 1e-15
+
+
+def test_encrypted_activation_matches_float():
+    wl = CONFIGS["small_block"]
+    p = wl.params()
+    o = Oracle(p)
+    level = p.num_q - 1
+    s, s_ntt = o.gen_secret(4000)
+    rlk = o.gen_relin_key(s_ntt, 4001)
+    x = np.random.default_rng(5).uniform(-1, 1, o.n)
+    scale = 2.0 ** 50
+    ct = o.encrypt(x, scale, level, s_ntt, 4002)
+    plan = o.act_schedule(level, scale)
+    out = o.poly_activation(ct, level, plan["k"], rlk)
+    assert out.shape == (2, plan["out_level"] + 1, o.N)
+    got = o.decrypt(out, plan["out_level"], s_ntt, plan["out_scale"])
+    assert np.abs(got - activation_reference(x)).max() < 1e-3
