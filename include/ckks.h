@@ -1,0 +1,175 @@
+/*
+ * ckks.h -- C boundary of the MI355X RNS-CKKS batched-convolution library.
+ *
+ * The operations are the ones the paper's batched convolution layer is made of (Methodology,
+ * "Convolution Layer": Rot, plaintext (.) ciphertext, accumulation; Eq. 8-11) and the RNS-CKKS
+ * primitives underneath them, which the paper uses through a library (Background: "Rotations and
+ * Key Switching", "RNS Decomposition and NTT Optimization"; Experiments, "HE Security Parameters":
+ * digit-decomposed key switching, rescaling), plus the ciphertext product that the polynomial
+ * activation needs ("Other Layers").  The server side only: key generation, encryption and
+ * decryption belong to the client (Threat Model) and are not part of this library.
+ *
+ * Conventions shared by every call
+ *   - Every function returns CKKS_OK (0) or a negative ckks_status; nothing throws or aborts.
+ *     ckks_last_error_string() gives the reason of the last failure on that context.
+ *   - Pointers named d_* are DEVICE pointers owned by the caller; pointers named h_* and all
+ *     structs are HOST memory.  Hot calls never allocate, free or synchronise: work is enqueued on
+ *     the caller's stream (a hipStream_t passed as void*, NULL = default stream) and scratch space
+ *     comes from the caller's workspace (d_ws, ws_bytes; size from ckks_workspace_bytes()).  The
+ *     caller keeps every buffer alive until the stream has drained.
+ *   - A polynomial limb is N uint64 residues in [0, q) (canonical on input and on output).
+ *     Polynomials are in evaluation (NTT) form: entry k of a limb is the value at
+ *     psi^(2*bitrev(k)+1), psi the 2N-th root given for that modulus.  ckks_ntt_fwd maps
+ *     natural-order coefficients to this order, ckks_ntt_inv maps back.
+ *   - Moduli are indexed q_0..q_L (num_q ciphertext primes) then p_0..p_{k-1} (num_p special primes).
+ *     A ciphertext at level l is uint64[2][l+1][N] (component, limb, coefficient), compact.
+ *     The scale of a ciphertext is a host-side double the caller tracks; the library is integer only.
+ *   - A switching key is uint64[dnum][2][num_q+num_p][N] in NTT form, component 0 = "b" part,
+ *     component 1 = "a" part; digit j covers limbs [j*alpha, (j+1)*alpha), alpha = ceil(num_q/dnum).
+ *     A key made for the top level serves every lower level.
+ *   - Outputs must not overlap inputs or the workspace unless a call says "in place".
+ */
+#ifndef CKKS_MI355X_H
+#define CKKS_MI355X_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum ckks_status {
+    CKKS_OK = 0,
+    CKKS_ERR_INVALID_ARG = -1,        /* null pointer, zero count, level out of range, ... */
+    CKKS_ERR_LEVEL_MISMATCH = -2,     /* operation needs a lower/higher level than given */
+    CKKS_ERR_UNSUPPORTED_PARAMS = -3, /* parameter set outside what the kernels handle */
+    CKKS_ERR_WORKSPACE_TOO_SMALL = -4,
+    CKKS_ERR_NO_KEY = -5,             /* key missing or made for another Galois element */
+    CKKS_ERR_HIP = -6                 /* a HIP runtime call failed */
+} ckks_status;
+
+typedef struct ckks_ctx ckks_ctx; /* immutable after creation; may be shared by concurrent calls */
+typedef struct ckks_key ckks_key;
+
+/* Parameter set.  Supported: 4 <= log_n <= 17; num_q >= 1; num_q + num_p <= 64; every modulus a
+ * prime below 2^58 with q = 1 mod 2N; psi[t]^N = -1 mod moduli[t]; dnum = 0 (no key switching,
+ * then num_p = 0) or 1 <= dnum <= num_q with num_p >= 1. */
+typedef struct ckks_params {
+    uint32_t log_n;
+    uint32_t num_q;
+    uint32_t num_p;
+    uint32_t dnum;
+    const uint64_t* moduli; /* host, num_q + num_p entries */
+    const uint64_t* psi;    /* host, primitive 2N-th root of unity per modulus */
+} ckks_params;
+
+/* Builds the context on the current HIP device: twiddle tables, reduction constants, basis-
+ * conversion tables for every level.  This is the only call that allocates device memory
+ * (about 32*N bytes per modulus) and it synchronises the device once. */
+int ckks_ctx_create(const ckks_params* params, ckks_ctx** out_ctx);
+void ckks_ctx_destroy(ckks_ctx* ctx);
+const char* ckks_last_error_string(const ckks_ctx* ctx);
+
+typedef enum ckks_op {
+    CKKS_OP_KEYSWITCH = 0,
+    CKKS_OP_ROTATE = 1,        /* count = number of rotations in the call */
+    CKKS_OP_RESCALE = 2,
+    CKKS_OP_CTCT_MUL_RELIN = 3,
+    CKKS_OP_POLY_ACT = 5       /* the convolution has its own query, he_conv_workspace_bytes() */
+} ckks_op;
+
+/* Bytes of workspace the given operation needs at `level` (0 on invalid arguments). */
+size_t ckks_workspace_bytes(const ckks_ctx* ctx, int op, uint32_t level, uint32_t count);
+
+/* Negacyclic NTT over Z_q[X]/(X^N+1) (Background, "RNS Decomposition and NTT Optimization").
+ * In place on batch*n_limbs consecutive limb-polys at d_polys; limb-poly number b*n_limbs+t uses
+ * modulus moduli[h_modulus_idx[t]].  fwd: natural-order coefficients -> evaluation form;
+ * inv: the exact inverse (includes 1/N). */
+int ckks_ntt_fwd(const ckks_ctx* ctx, uint64_t* d_polys, const uint32_t* h_modulus_idx,
+                 uint32_t n_limbs, uint32_t batch, void* stream);
+int ckks_ntt_inv(const ckks_ctx* ctx, uint64_t* d_polys, const uint32_t* h_modulus_idx,
+                 uint32_t n_limbs, uint32_t batch, void* stream);
+
+/* Wraps a caller-owned switching key (no copy).  galois_elt = 5^r mod 2N for the key of a rotation
+ * by r slots, 0 for the relinearisation key (s^2 -> s). */
+int ckks_key_load(const ckks_ctx* ctx, const uint64_t* d_key, uint32_t galois_elt, ckks_key** out_key);
+void ckks_key_free(ckks_key* key);
+
+/* Galois element of a left rotation by `offset` slots (negative = right): 5^offset mod 2N. */
+uint32_t ckks_galois_element(const ckks_ctx* ctx, int32_t offset);
+
+/* Hybrid key switch of one polynomial (Background, "Rotations and Key Switching"):
+ * d_c uint64[level+1][N] -> d_out uint64[2][level+1][N] with out0 + out1*s = c*s' + small noise,
+ * s' the secret the key was made for.  Steps: per digit iNTT and basis extension to the live
+ * q-limbs and the special primes (plain, uncorrected sum), NTT, inner product with the key,
+ * division by P (floor-like, uncorrected). */
+int ckks_keyswitch(const ckks_ctx* ctx, const uint64_t* d_c, uint32_t level, const ckks_key* key,
+                   uint64_t* d_out, void* d_ws, size_t ws_bytes, void* stream);
+
+/* Rot(ct, r) for n_rot offsets of one ciphertext (Eq. 8-10): slot i of output t holds slot
+ * (i + h_offsets[t]) mod N/2 of the input.  keys[t] must carry the Galois element of h_offsets[t];
+ * an offset that is 0 mod N/2 is a plain copy and needs no key (keys[t] may be NULL).
+ * hoisted = 1: c1 is decomposed and extended once and every rotation permutes the extended digits
+ * ("fast rotations"); hoisted = 0: each rotation permutes the ciphertext and key-switches the
+ * permuted c1.  The two orders give different residues that decrypt to the same slots up to noise.
+ * h_d_outs: host array of n_rot device pointers, each uint64[2][level+1][N]. */
+int ckks_rotate_hoisted(const ckks_ctx* ctx, const uint64_t* d_ct, uint32_t level,
+                        const int32_t* h_offsets, uint32_t n_rot, const ckks_key* const* keys,
+                        uint64_t* const* h_d_outs, int hoisted, void* d_ws, size_t ws_bytes, void* stream);
+
+/* Plaintext-ciphertext multiply-accumulate (Eq. 11 and the channel sum after it):
+ * acc[c][i][x] = (accumulate ? acc[c][i][x] : 0) + sum_k pt_k[i][x] * ct_k[c][i][x]  mod q_i.
+ * h_d_pts / h_d_cts: host arrays of n_terms device pointers (uint64[level+1][N] and
+ * uint64[2][level+1][N]).  d_acc may not overlap any operand. */
+int ckks_ptct_mac(const ckks_ctx* ctx, const uint64_t* const* h_d_pts, const uint64_t* const* h_d_cts,
+                  uint32_t n_terms, uint32_t level, uint64_t* d_acc, int accumulate, void* stream);
+
+/* Rescale (Experiments, "HE Security Parameters"): divide by q_level with rounding to nearest and
+ * drop that limb.  d_ct uint64[2][level+1][N] -> d_out uint64[2][level][N]; level >= 1.
+ * The caller divides the scale by q_level. */
+int ckks_rescale(const ckks_ctx* ctx, const uint64_t* d_ct, uint32_t level, uint64_t* d_out,
+                 void* d_ws, size_t ws_bytes, void* stream);
+
+/* Ciphertext product with relinearisation ("Other Layers": polynomial activation):
+ * (d0, d1, d2) = (a0 b0, a0 b1 + a1 b0, a1 b1); out = (d0, d1) + KeySwitch(d2, rlk).  No rescale.
+ * rlk must be the relinearisation key (galois_elt 0).  d_a may equal d_b. */
+int ckks_ctct_mul_relin(const ckks_ctx* ctx, const uint64_t* d_a, const uint64_t* d_b, uint32_t level,
+                        const ckks_key* rlk, uint64_t* d_out, void* d_ws, size_t ws_bytes, void* stream);
+
+/* Batched 3x3 convolution layer, stride 1, zero padding 1, on channel-by-channel packed
+ * ciphertexts (Eqs. 2-5: ciphertext c holds channel c of all `batch` images, image j in slots
+ * [j*H*W, (j+1)*H*W); Eqs. 6-7, 10, 11):
+ *   out_o = Rescale( sum_{c < C_in} sum_{tap} pt[o,c,tap] (.) Rot(in_c, dy*W + dx) ),  tap = (dy,dx)
+ * in row-major order over {-1,0,1}^2.  The weight plaintexts are given in factored form,
+ *   pt[o,c,tap] = w_int[o,c,tap] * M_tap  (mod q_i),
+ * M_tap = d_tap_masks[tap] the encoded 0/1 validity mask of the tap (uint64[9][level+1][N], NTT
+ * form) and w_int the integer weight, given by its residues d_w_res uint64[C_out][C_in][9][level+1].
+ * rot_keys[tap] is the key of offset dy*W+dx (entry 4, the centre, is ignored).  The eight
+ * rotations of each input share one decomposition (hoisted).
+ * h_d_in: C_in device pointers uint64[2][level+1][N]; h_d_out: C_out device pointers
+ * uint64[2][level][N].  Fails with CKKS_ERR_INVALID_ARG if H*W*batch > N/2 (Eq. 4). */
+typedef struct he_conv_desc {
+    uint32_t c_in, c_out, height, width, batch, level;
+} he_conv_desc;
+
+/* Workspace bytes he_conv_batched needs for this shape (0 on invalid arguments): the shared
+ * decomposition, 9*C_in masked aligned ciphertexts, C_out accumulators and rescale scratch. */
+size_t he_conv_workspace_bytes(const ckks_ctx* ctx, const he_conv_desc* desc);
+
+int he_conv_batched(const ckks_ctx* ctx, const he_conv_desc* desc, const uint64_t* const* h_d_in,
+                    const ckks_key* const* rot_keys, const uint64_t* d_tap_masks, const uint64_t* d_w_res,
+                    uint64_t* const* h_d_out, void* d_ws, size_t ws_bytes, void* stream);
+
+/* Odd degree-7 polynomial activation on one ciphertext with four ciphertext products
+ * ("Other Layers"):  x2 = x*x, x3 = x2*x, x4 = x2*x2 (each rescaled once),
+ *   B = Rescale(k[2]*x + k[3]*x3),  y = Rescale((k[0]*x + k[1]*x3) + x4*B).
+ * h_k: four signed integers that fold the polynomial coefficients and the scale ratios (the caller
+ * tracks scales).  d_x uint64[2][level+1][N], level >= 4  ->  d_out uint64[2][level-3][N]. */
+int he_poly_act_deg7(const ckks_ctx* ctx, const uint64_t* d_x, uint32_t level, const int64_t* h_k,
+                     const ckks_key* rlk, uint64_t* d_out, void* d_ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CKKS_MI355X_H */

@@ -1,0 +1,333 @@
+"""Thin ctypes binding of the C boundary declared in ``include/ckks.h``.
+
+Argument marshalling only: every function below has the name of the C entry point it calls and
+hands it raw device pointers of PyTorch tensors (PyTorch is used for device memory and streams,
+nothing else).  Polynomial data are ``torch.int64`` tensors holding the uint64 residues bit for
+bit (``from_host`` / ``to_host`` convert from and to numpy ``uint64``).  There is no fallback: if
+the compiled library is missing the import of this module fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libckks_mi355x.so")
+
+CKKS_OK = 0
+CKKS_ERR_INVALID_ARG = -1
+CKKS_ERR_LEVEL_MISMATCH = -2
+CKKS_ERR_UNSUPPORTED_PARAMS = -3
+CKKS_ERR_WORKSPACE_TOO_SMALL = -4
+CKKS_ERR_NO_KEY = -5
+CKKS_ERR_HIP = -6
+
+CKKS_OP_KEYSWITCH = 0
+CKKS_OP_ROTATE = 1
+CKKS_OP_RESCALE = 2
+CKKS_OP_CTCT_MUL_RELIN = 3
+CKKS_OP_POLY_ACT = 5
+
+EXPORTS = (
+    "ckks_ctx_create", "ckks_ctx_destroy", "ckks_last_error_string", "ckks_workspace_bytes",
+    "ckks_ntt_fwd", "ckks_ntt_inv", "ckks_key_load", "ckks_key_free", "ckks_galois_element",
+    "ckks_keyswitch", "ckks_rotate_hoisted", "ckks_ptct_mac", "ckks_rescale", "ckks_ctct_mul_relin",
+    "he_conv_workspace_bytes", "he_conv_batched", "he_poly_act_deg7",
+)
+
+_expect_device = "cuda"  # tensors handed to the library must live here
+
+
+class CkksError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"ckks status {code}: {message}")
+        self.code = code
+
+
+class _Params(C.Structure):
+    _fields_ = [("log_n", C.c_uint32), ("num_q", C.c_uint32), ("num_p", C.c_uint32), ("dnum", C.c_uint32),
+                ("moduli", C.POINTER(C.c_uint64)), ("psi", C.POINTER(C.c_uint64))]
+
+
+class _ConvDesc(C.Structure):
+    _fields_ = [("c_in", C.c_uint32), ("c_out", C.c_uint32), ("height", C.c_uint32), ("width", C.c_uint32),
+                ("batch", C.c_uint32), ("level", C.c_uint32)]
+
+
+def _bind(path: str):
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()')")
+    lib = C.CDLL(path)
+    vp, u32, i32, sz = C.c_void_p, C.c_uint32, C.c_int, C.c_size_t
+    lib.ckks_ctx_create.argtypes = [C.POINTER(_Params), C.POINTER(vp)]
+    lib.ckks_ctx_destroy.argtypes = [vp]
+    lib.ckks_ctx_destroy.restype = None
+    lib.ckks_last_error_string.argtypes = [vp]
+    lib.ckks_last_error_string.restype = C.c_char_p
+    lib.ckks_workspace_bytes.argtypes = [vp, i32, u32, u32]
+    lib.ckks_workspace_bytes.restype = sz
+    for f in (lib.ckks_ntt_fwd, lib.ckks_ntt_inv):
+        f.argtypes = [vp, vp, C.POINTER(u32), u32, u32, vp]
+    lib.ckks_key_load.argtypes = [vp, vp, u32, C.POINTER(vp)]
+    lib.ckks_key_free.argtypes = [vp]
+    lib.ckks_key_free.restype = None
+    lib.ckks_galois_element.argtypes = [vp, C.c_int32]
+    lib.ckks_galois_element.restype = u32
+    lib.ckks_keyswitch.argtypes = [vp, vp, u32, vp, vp, vp, sz, vp]
+    lib.ckks_rotate_hoisted.argtypes = [vp, vp, u32, C.POINTER(C.c_int32), u32, C.POINTER(vp), C.POINTER(vp), i32, vp, sz, vp]
+    lib.ckks_ptct_mac.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), u32, u32, vp, i32, vp]
+    lib.ckks_rescale.argtypes = [vp, vp, u32, vp, vp, sz, vp]
+    lib.ckks_ctct_mul_relin.argtypes = [vp, vp, vp, u32, vp, vp, vp, sz, vp]
+    lib.he_conv_workspace_bytes.argtypes = [vp, C.POINTER(_ConvDesc)]
+    lib.he_conv_workspace_bytes.restype = sz
+    lib.he_conv_batched.argtypes = [vp, C.POINTER(_ConvDesc), C.POINTER(vp), C.POINTER(vp), vp, vp, C.POINTER(vp), vp, sz, vp]
+    lib.he_poly_act_deg7.argtypes = [vp, vp, u32, C.POINTER(C.c_int64), vp, vp, vp, sz, vp]
+    return lib
+
+
+_lib = _bind(LIB_PATH)
+
+
+# --------------------------------------------------------------------------------------- helpers
+def from_host(a: np.ndarray) -> torch.Tensor:
+    """numpy uint64 array -> int64 tensor with the same bits on the device."""
+    a = np.ascontiguousarray(a, dtype=np.uint64)
+    return torch.from_numpy(a.view(np.int64)).to(_expect_device)
+
+
+def to_host(t: torch.Tensor) -> np.ndarray:
+    return t.detach().cpu().contiguous().numpy().view(np.uint64)
+
+
+def empty(*shape) -> torch.Tensor:
+    return torch.empty(*shape, dtype=torch.int64, device=_expect_device)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    if t.device.type != _expect_device or t.dtype not in (torch.int64, torch.uint64, torch.uint8) or not t.is_contiguous():
+        raise ValueError(f"need a contiguous int64 tensor on {_expect_device}")
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is not None:
+        return int(stream)
+    if _expect_device == "cuda":
+        return torch.cuda.current_stream().cuda_stream
+    return None
+
+
+def _ptr_array(ptrs: Sequence[Optional[int]]):
+    return (C.c_void_p * len(ptrs))(*ptrs)
+
+
+class Key:
+    """Handle of a caller-owned switching key (keeps the tensor alive)."""
+
+    def __init__(self, ctx: "Context", tensor: torch.Tensor, galois_elt: int):
+        self.tensor = tensor
+        self.galois_elt = galois_elt
+        self._ctx = ctx
+        h = C.c_void_p()
+        ctx._check(_lib.ckks_key_load(ctx.handle, _ptr(tensor), galois_elt, C.byref(h)))
+        self.handle = h
+
+    def __del__(self):
+        try:
+            _lib.ckks_key_free(self.handle)
+        except Exception:
+            pass
+
+
+class Context:
+    """Owns a ``ckks_ctx`` (immutable tables on the current device)."""
+
+    def __init__(self, params):
+        self.log_n, self.num_q, self.num_p, self.dnum = int(params.log_n), int(params.num_q), int(params.num_p), int(params.dnum)
+        self.N = 1 << self.log_n
+        self.moduli = [int(q) for q in params.moduli]
+        self._mods = (C.c_uint64 * len(self.moduli))(*self.moduli)
+        self._psi = (C.c_uint64 * len(self.moduli))(*[int(x) for x in params.psi])
+        p = _Params(self.log_n, self.num_q, self.num_p, self.dnum, self._mods, self._psi)
+        h = C.c_void_p()
+        rc = _lib.ckks_ctx_create(C.byref(p), C.byref(h))
+        if rc != CKKS_OK:
+            raise CkksError(rc, _lib.ckks_last_error_string(None).decode())
+        self.handle = h
+        self._ws: Optional[torch.Tensor] = None
+
+    def __del__(self):
+        try:
+            _lib.ckks_ctx_destroy(self.handle)
+        except Exception:
+            pass
+
+    def _check(self, rc: int):
+        if rc != CKKS_OK:
+            raise CkksError(rc, _lib.ckks_last_error_string(self.handle).decode())
+
+    def workspace(self, nbytes: int) -> torch.Tensor:
+        """A cached scratch tensor of at least nbytes (grown on demand, reused across calls)."""
+        if self._ws is None or self._ws.numel() < nbytes:
+            self._ws = torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=_expect_device)
+        return self._ws
+
+
+# ------------------------------------------------------------------ the C entry points, by name
+def ckks_workspace_bytes(ctx: Context, op: int, level: int, count: int = 1) -> int:
+    return int(_lib.ckks_workspace_bytes(ctx.handle, op, level, count))
+
+
+def ckks_galois_element(ctx: Context, offset: int) -> int:
+    return int(_lib.ckks_galois_element(ctx.handle, offset))
+
+
+def ckks_key_load(ctx: Context, key: torch.Tensor, galois_elt: int) -> Key:
+    return Key(ctx, key, galois_elt)
+
+
+def _ntt(fn, ctx, polys, modulus_idx, batch, stream):
+    n_limbs = len(modulus_idx)
+    if batch is None:
+        batch = polys.numel() // (n_limbs * ctx.N)
+    if polys.numel() != batch * n_limbs * ctx.N:
+        raise ValueError("tensor size does not match batch * n_limbs * N")
+    idx = (C.c_uint32 * n_limbs)(*[int(i) for i in modulus_idx])
+    ctx._check(fn(ctx.handle, _ptr(polys), idx, n_limbs, batch, _stream(stream)))
+    return polys
+
+
+def ckks_ntt_fwd(ctx: Context, polys: torch.Tensor, modulus_idx: Sequence[int], batch: Optional[int] = None, stream=None):
+    """In place on [batch][len(modulus_idx)][N]."""
+    return _ntt(_lib.ckks_ntt_fwd, ctx, polys, modulus_idx, batch, stream)
+
+
+def ckks_ntt_inv(ctx: Context, polys: torch.Tensor, modulus_idx: Sequence[int], batch: Optional[int] = None, stream=None):
+    return _ntt(_lib.ckks_ntt_inv, ctx, polys, modulus_idx, batch, stream)
+
+
+def _ws(ctx: Context, ws: Optional[torch.Tensor], need: int) -> torch.Tensor:
+    return ctx.workspace(need) if ws is None else ws
+
+
+def ckks_keyswitch(ctx: Context, c: torch.Tensor, level: int, key: Key, out: Optional[torch.Tensor] = None,
+                   ws: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    if c.numel() != (level + 1) * ctx.N:
+        raise ValueError("c must be [level+1][N]")
+    if out is None:
+        out = empty(2, level + 1, ctx.N)
+    ws = _ws(ctx, ws, ckks_workspace_bytes(ctx, CKKS_OP_KEYSWITCH, level))
+    ctx._check(_lib.ckks_keyswitch(ctx.handle, _ptr(c), level, key.handle if key else None, _ptr(out), _ptr(ws), ws.numel(), _stream(stream)))
+    return out
+
+
+def ckks_rotate_hoisted(ctx: Context, ct: torch.Tensor, level: int, offsets: Sequence[int], keys: Sequence[Optional[Key]],
+                        hoisted: bool = True, outs: Optional[List[torch.Tensor]] = None, ws: Optional[torch.Tensor] = None,
+                        stream=None) -> List[torch.Tensor]:
+    n = len(offsets)
+    if ct.numel() != 2 * (level + 1) * ctx.N or len(keys) != n:
+        raise ValueError("ct must be [2][level+1][N] and one key per offset")
+    if outs is None:
+        outs = [empty(2, level + 1, ctx.N) for _ in range(n)]
+    for o in outs:
+        if o.numel() != 2 * (level + 1) * ctx.N:
+            raise ValueError("each output must be [2][level+1][N]")
+    ws = _ws(ctx, ws, ckks_workspace_bytes(ctx, CKKS_OP_ROTATE, level, n))
+    offs = (C.c_int32 * n)(*[int(r) for r in offsets])
+    ks = _ptr_array([k.handle.value if k is not None else None for k in keys])
+    os_ = _ptr_array([_ptr(o) for o in outs])
+    ctx._check(_lib.ckks_rotate_hoisted(ctx.handle, _ptr(ct), level, offs, n, ks, os_, int(bool(hoisted)), _ptr(ws), ws.numel(), _stream(stream)))
+    return outs
+
+
+def ckks_ptct_mac(ctx: Context, pts: Sequence[torch.Tensor], cts: Sequence[torch.Tensor], level: int,
+                  acc: Optional[torch.Tensor] = None, accumulate: bool = False, stream=None) -> torch.Tensor:
+    n = len(pts)
+    if len(cts) != n:
+        raise ValueError("one plaintext per ciphertext")
+    for p_, c_ in zip(pts, cts):
+        if p_.numel() != (level + 1) * ctx.N or c_.numel() != 2 * (level + 1) * ctx.N:
+            raise ValueError("operands must be [level+1][N] and [2][level+1][N]")
+    if acc is None:
+        if accumulate:
+            raise ValueError("accumulate needs an accumulator")
+        acc = empty(2, level + 1, ctx.N)
+    elif acc.numel() != 2 * (level + 1) * ctx.N:
+        raise ValueError("acc must be [2][level+1][N]")
+    pa = _ptr_array([_ptr(p_) for p_ in pts])
+    ca = _ptr_array([_ptr(c_) for c_ in cts])
+    ctx._check(_lib.ckks_ptct_mac(ctx.handle, pa, ca, n, level, _ptr(acc), int(bool(accumulate)), _stream(stream)))
+    return acc
+
+
+def ckks_rescale(ctx: Context, ct: torch.Tensor, level: int, out: Optional[torch.Tensor] = None,
+                 ws: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    if ct.numel() != 2 * (level + 1) * ctx.N:
+        raise ValueError("ct must be [2][level+1][N]")
+    if out is None:
+        out = empty(2, max(level, 1), ctx.N)
+    ws = _ws(ctx, ws, ckks_workspace_bytes(ctx, CKKS_OP_RESCALE, level))
+    ctx._check(_lib.ckks_rescale(ctx.handle, _ptr(ct), level, _ptr(out), _ptr(ws), ws.numel(), _stream(stream)))
+    return out
+
+
+def ckks_ctct_mul_relin(ctx: Context, a: torch.Tensor, b: torch.Tensor, level: int, rlk: Key,
+                        out: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    if a.numel() != 2 * (level + 1) * ctx.N or b.numel() != a.numel():
+        raise ValueError("operands must be [2][level+1][N]")
+    if out is None:
+        out = empty(2, level + 1, ctx.N)
+    ws = _ws(ctx, ws, ckks_workspace_bytes(ctx, CKKS_OP_CTCT_MUL_RELIN, level))
+    ctx._check(_lib.ckks_ctct_mul_relin(ctx.handle, _ptr(a), _ptr(b), level, rlk.handle if rlk else None, _ptr(out), _ptr(ws), ws.numel(), _stream(stream)))
+    return out
+
+
+def he_conv_workspace_bytes(ctx: Context, c_in: int, c_out: int, height: int, width: int, batch: int, level: int) -> int:
+    d = _ConvDesc(c_in, c_out, height, width, batch, level)
+    return int(_lib.he_conv_workspace_bytes(ctx.handle, C.byref(d)))
+
+
+def he_conv_batched(ctx: Context, height: int, width: int, batch: int, level: int, ins: Sequence[torch.Tensor],
+                    rot_keys: Sequence[Optional[Key]], tap_masks: torch.Tensor, w_res: torch.Tensor, c_out: int,
+                    outs: Optional[List[torch.Tensor]] = None, ws: Optional[torch.Tensor] = None, stream=None) -> List[torch.Tensor]:
+    """ins: C_in tensors [2][level+1][N]; rot_keys: nine entries in tap order (centre ignored);
+    tap_masks [9][level+1][N]; w_res [C_out][C_in][9][level+1] residues of the integer weights."""
+    c_in = len(ins)
+    L1 = level + 1
+    if len(rot_keys) != 9:
+        raise ValueError("nine rotation-key entries expected (row-major taps, centre may be None)")
+    if tap_masks.numel() != 9 * L1 * ctx.N or w_res.numel() != c_out * c_in * 9 * L1:
+        raise ValueError("tap_masks must be [9][level+1][N] and w_res [C_out][C_in][9][level+1]")
+    for t in ins:
+        if t.numel() != 2 * L1 * ctx.N:
+            raise ValueError("each input must be [2][level+1][N]")
+    if outs is None:
+        outs = [empty(2, max(level, 1), ctx.N) for _ in range(c_out)]
+    for o in outs:
+        if o.numel() != 2 * level * ctx.N:
+            raise ValueError("each output must be [2][level][N]")
+    d = _ConvDesc(c_in, c_out, height, width, batch, level)
+    ws = _ws(ctx, ws, he_conv_workspace_bytes(ctx, c_in, c_out, height, width, batch, level))
+    ia = _ptr_array([_ptr(t) for t in ins])
+    ka = _ptr_array([k.handle.value if k is not None else None for k in rot_keys])
+    oa = _ptr_array([_ptr(o) for o in outs])
+    ctx._check(_lib.he_conv_batched(ctx.handle, C.byref(d), ia, ka, _ptr(tap_masks), _ptr(w_res), oa, _ptr(ws), ws.numel(), _stream(stream)))
+    return outs
+
+
+def he_poly_act_deg7(ctx: Context, x: torch.Tensor, level: int, k: Sequence[int], rlk: Key, out: Optional[torch.Tensor] = None,
+                     ws: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    if x.numel() != 2 * (level + 1) * ctx.N or len(k) != 4:
+        raise ValueError("x must be [2][level+1][N] and k four integers")
+    if out is None:
+        out = empty(2, max(level - 3, 1), ctx.N)
+    ws = _ws(ctx, ws, ckks_workspace_bytes(ctx, CKKS_OP_POLY_ACT, level))
+    ka = (C.c_int64 * 4)(*[int(v) for v in k])
+    ctx._check(_lib.he_poly_act_deg7(ctx.handle, _ptr(x), level, ka, rlk.handle if rlk else None, _ptr(out), _ptr(ws), ws.numel(), _stream(stream)))
+    return out

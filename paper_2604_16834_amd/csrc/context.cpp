@@ -1,0 +1,216 @@
+// Context creation: validates the parameter set and builds every table the kernels read
+// (twiddles with Shoup companions, Barrett constants, basis-conversion constants for ModUp at every
+// level, ModDown and rescale constants).  Host-side integer arithmetic with 128-bit products.
+#include <cstring>
+#include <new>
+
+#include "ctx.h"
+
+typedef unsigned __int128 u128;
+
+static u64 h_mulmod(u64 a, u64 b, u64 q) { return (u64)((u128)a * b % q); }
+static u64 h_powmod(u64 a, u64 e, u64 q) {
+    u64 r = 1 % q;
+    a %= q;
+    for (; e; e >>= 1) {
+        if (e & 1) r = h_mulmod(r, a, q);
+        a = h_mulmod(a, a, q);
+    }
+    return r;
+}
+static u64 h_invmod(u64 a, u64 q) { return h_powmod(a, q - 2, q); }
+static u64 h_shoup(u64 w, u64 q) { return (u64)(((u128)w << 64) / q); }
+static u32 h_bits(u64 v) { u32 b = 0; while (v) { b++; v >>= 1; } return b; }
+static u32 h_bitrev(u32 x, u32 bits) {
+    u32 r = 0;
+    for (u32 i = 0; i < bits; i++) { r = (r << 1) | (x & 1); x >>= 1; }
+    return r;
+}
+static bool h_is_prime(u64 n) {
+    if (n < 2) return false;
+    static const u64 bases[] = {2, 3, 5, 7, 11, 13, 17, 19, 23, 29, 31, 37};
+    for (u64 p : bases) { if (n % p == 0) return n == p; }
+    u64 d = n - 1; u32 s = 0;
+    while (!(d & 1)) { d >>= 1; s++; }
+    for (u64 a : bases) {
+        u64 x = h_powmod(a, d, n);
+        if (x == 1 || x == n - 1) continue;
+        bool comp = true;
+        for (u32 r = 1; r < s; r++) { x = h_mulmod(x, x, n); if (x == n - 1) { comp = false; break; } }
+        if (comp) return false;
+    }
+    return true;
+}
+
+template <class T>
+static hipError_t upload(const std::vector<T>& h, T** d) {
+    *d = nullptr;
+    if (h.empty()) return hipSuccess;
+    hipError_t e = hipMalloc((void**)d, h.size() * sizeof(T));
+    if (e != hipSuccess) return e;
+    return hipMemcpy(*d, h.data(), h.size() * sizeof(T), hipMemcpyHostToDevice);
+}
+
+static thread_local std::string g_create_error;
+
+extern "C" const char* ckks_last_error_string(const ckks_ctx* ctx) {
+    return ctx ? ctx->err.c_str() : g_create_error.c_str();
+}
+
+extern "C" void ckks_ctx_destroy(ckks_ctx* c) {
+    if (!c) return;
+    (void)hipFree(c->d_mc);
+    (void)hipFree(c->d_tw);
+    (void)hipFree(c->d_tw_sh);
+    (void)hipFree(c->d_itw);
+    (void)hipFree(c->d_itw_sh);
+    (void)hipFree(c->d_modup);
+    (void)hipFree(c->d_moddown);
+    (void)hipFree(c->d_rescale);
+    delete c;
+}
+
+extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
+    auto fail = [&](int code, const char* msg) { g_create_error = msg; return code; };
+    if (!p || !out || !p->moduli || !p->psi) return fail(CKKS_ERR_INVALID_ARG, "null argument");
+    *out = nullptr;
+    if (p->log_n < 4 || p->log_n > 17) return fail(CKKS_ERR_UNSUPPORTED_PARAMS, "log_n must be in [4, 17]");
+    const u32 M = p->num_q + p->num_p;
+    if (p->num_q < 1 || M > CKKS_MAX_MODULI) return fail(CKKS_ERR_UNSUPPORTED_PARAMS, "need 1 <= num_q and num_q + num_p <= 64");
+    if (p->dnum == 0 && p->num_p != 0) return fail(CKKS_ERR_INVALID_ARG, "special primes given but dnum = 0");
+    if (p->dnum != 0 && (p->dnum > p->num_q || p->num_p < 1)) return fail(CKKS_ERR_INVALID_ARG, "need 1 <= dnum <= num_q and num_p >= 1");
+    const u32 N = 1u << p->log_n;
+    const u32 alpha = p->dnum ? (p->num_q + p->dnum - 1) / p->dnum : 0;
+    if (alpha > 16 || p->num_p > 16) return fail(CKKS_ERR_UNSUPPORTED_PARAMS, "at most 16 limbs per digit and 16 special primes");
+    u32 bmin = 64, bmax = 0;
+    for (u32 t = 0; t < M; t++) {
+        const u64 q = p->moduli[t];
+        if (q >= (1ull << 58) || q < 1024) return fail(CKKS_ERR_UNSUPPORTED_PARAMS, "moduli must lie in [2^10, 2^58)");
+        if ((q - 1) % (2ull * N) != 0) return fail(CKKS_ERR_INVALID_ARG, "modulus is not 1 mod 2N");
+        if (!h_is_prime(q)) return fail(CKKS_ERR_INVALID_ARG, "modulus is not prime");
+        for (u32 u = 0; u < t; u++)
+            if (p->moduli[u] == q) return fail(CKKS_ERR_INVALID_ARG, "moduli must be distinct");
+        if (p->psi[t] >= q || h_powmod(p->psi[t], N, q) != q - 1) return fail(CKKS_ERR_INVALID_ARG, "psi is not a primitive 2N-th root of unity");
+        const u32 b = h_bits(q);
+        bmin = b < bmin ? b : bmin;
+        bmax = b > bmax ? b : bmax;
+    }
+    // products of two residues are below 2^(2*bmax); a Barrett input must stay below 2^(62+bmin)
+    const int lazy_log = 62 + (int)bmin - 2 * (int)bmax;
+    if (lazy_log < 4) return fail(CKKS_ERR_UNSUPPORTED_PARAMS, "moduli sizes too uneven for 128-bit lazy accumulation");
+
+    ckks_ctx* c = new (std::nothrow) ckks_ctx;
+    if (!c) return fail(CKKS_ERR_INVALID_ARG, "out of host memory");
+    c->log_n = p->log_n; c->N = N; c->num_q = p->num_q; c->num_p = p->num_p; c->dnum = p->dnum; c->alpha = alpha; c->M = M;
+    c->log_lo = p->log_n < CKKS_TILE_LOG ? p->log_n : CKKS_TILE_LOG;
+    c->log_hi = p->log_n - c->log_lo;
+    c->lazy_terms = 1u << (lazy_log > 12 ? 12 : lazy_log);
+    c->mod.assign(p->moduli, p->moduli + M);
+    c->psi.assign(p->psi, p->psi + M);
+
+    c->mc.resize(M);
+    std::vector<u64> tw((size_t)M * N), tw_sh((size_t)M * N), itw((size_t)M * N), itw_sh((size_t)M * N);
+    for (u32 t = 0; t < M; t++) {
+        const u64 q = c->mod[t];
+        ModConst& m = c->mc[t];
+        m.q = q;
+        m.sh = h_bits(q) - 2;
+        m.mu = (u64)((((u128)1) << (64 + m.sh)) / q);
+        m.pad = 0;
+        m.n_inv = h_invmod(N % q, q);
+        m.n_inv_sh = h_shoup(m.n_inv, q);
+        std::vector<u64> pw(N);
+        pw[0] = 1;
+        for (u32 i = 1; i < N; i++) pw[i] = h_mulmod(pw[i - 1], c->psi[t], q);
+        const u64 psi_inv = h_invmod(c->psi[t], q);
+        std::vector<u64> ipw(N);
+        ipw[0] = 1;
+        for (u32 i = 1; i < N; i++) ipw[i] = h_mulmod(ipw[i - 1], psi_inv, q);
+        for (u32 i = 0; i < N; i++) {
+            const u32 r = h_bitrev(i, p->log_n);
+            const size_t o = (size_t)t * N + i;
+            tw[o] = pw[r]; tw_sh[o] = h_shoup(pw[r], q);
+            itw[o] = ipw[r]; itw_sh[o] = h_shoup(ipw[r], q);
+        }
+    }
+
+    // ModUp tables, one per (level, digit): the digit modulus is the product of the digit's LIVE limbs
+    std::vector<u64> modup;
+    if (c->dnum) {
+        modup.assign((size_t)c->num_q * c->modup_level_stride(), 0);
+        for (u32 level = 0; level < c->num_q; level++)
+            for (u32 j = 0; j < c->live_digits(level); j++) {
+                u64* tab = modup.data() + level * c->modup_level_stride() + j * c->modup_digit_stride();
+                const u32 lo = c->digit_lo(j), hi = c->digit_hi(j, level), E = c->ext_limbs(level);
+                for (u32 a = 0; a < hi - lo; a++) {
+                    const u64 qa = c->mod[lo + a];
+                    u64 qhat = 1;
+                    for (u32 b = lo; b < hi; b++) if (b != lo + a) qhat = h_mulmod(qhat, c->mod[b] % qa, qa);
+                    const u64 inv = h_invmod(qhat, qa);
+                    tab[a] = inv;
+                    tab[alpha + a] = h_shoup(inv, qa);
+                    for (u32 e = 0; e < E; e++) {
+                        const u64 qt = c->mod[c->ext_modulus(level, e)];
+                        u64 v = 1;
+                        for (u32 b = lo; b < hi; b++) if (b != lo + a) v = h_mulmod(v, c->mod[b] % qt, qt);
+                        tab[2 * alpha + (size_t)a * M + e] = v;
+                    }
+                }
+            }
+    }
+    // ModDown table
+    std::vector<u64> moddown;
+    if (c->dnum) {
+        const u32 k = c->num_p, nq = c->num_q;
+        moddown.assign(2 * k + (size_t)k * nq + 2 * nq, 0);
+        for (u32 a = 0; a < k; a++) {
+            const u64 pa = c->mod[nq + a];
+            u64 phat = 1;
+            for (u32 b = 0; b < k; b++) if (b != a) phat = h_mulmod(phat, c->mod[nq + b] % pa, pa);
+            const u64 inv = h_invmod(phat, pa);
+            moddown[a] = inv;
+            moddown[k + a] = h_shoup(inv, pa);
+            for (u32 i = 0; i < nq; i++) {
+                const u64 qi = c->mod[i];
+                u64 v = 1;
+                for (u32 b = 0; b < k; b++) if (b != a) v = h_mulmod(v, c->mod[nq + b] % qi, qi);
+                moddown[2 * k + (size_t)a * nq + i] = v;
+            }
+        }
+        for (u32 i = 0; i < nq; i++) {
+            const u64 qi = c->mod[i];
+            u64 P = 1;
+            for (u32 b = 0; b < k; b++) P = h_mulmod(P, c->mod[nq + b] % qi, qi);
+            const u64 pinv = h_invmod(P, qi);
+            moddown[2 * k + (size_t)k * nq + i] = pinv;
+            moddown[2 * k + (size_t)k * nq + nq + i] = h_shoup(pinv, qi);
+        }
+    }
+    // rescale table [l][i] = (q_l^-1 mod q_i, Shoup companion, q_l mod q_i)
+    std::vector<u64> resc((size_t)c->num_q * c->num_q * 3, 0);
+    for (u32 l = 0; l < c->num_q; l++)
+        for (u32 i = 0; i < l; i++) {
+            const u64 qi = c->mod[i], ql = c->mod[l] % qi;
+            const u64 inv = h_invmod(ql, qi);
+            u64* t = resc.data() + ((size_t)l * c->num_q + i) * 3;
+            t[0] = inv; t[1] = h_shoup(inv, qi); t[2] = ql;
+        }
+
+    hipError_t e = hipSuccess;
+    if (e == hipSuccess) e = upload(c->mc, &c->d_mc);
+    if (e == hipSuccess) e = upload(tw, &c->d_tw);
+    if (e == hipSuccess) e = upload(tw_sh, &c->d_tw_sh);
+    if (e == hipSuccess) e = upload(itw, &c->d_itw);
+    if (e == hipSuccess) e = upload(itw_sh, &c->d_itw_sh);
+    if (e == hipSuccess) e = upload(modup, &c->d_modup);
+    if (e == hipSuccess) e = upload(moddown, &c->d_moddown);
+    if (e == hipSuccess) e = upload(resc, &c->d_rescale);
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+        g_create_error = std::string("HIP error while building tables: ") + hipGetErrorString(e);
+        ckks_ctx_destroy(c);
+        return CKKS_ERR_HIP;
+    }
+    *out = c;
+    return CKKS_OK;
+}

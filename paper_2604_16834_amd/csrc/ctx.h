@@ -1,0 +1,83 @@
+// Internal: the immutable context (host mirror + device tables) and the kernel launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <string>
+#include <vector>
+
+#include "../../include/ckks.h"
+#include "modarith.h"
+
+#define CKKS_MAX_MODULI 64
+#define CKKS_TILE_LOG 11  // one workgroup transforms 2^11 points held in LDS
+
+// Which limb-polys a batched kernel touches: entry a of the list reads the poly at position
+// spos[a] of the source block and writes position dpos[a] of the destination block, modulo
+// moduli[mod[a]].  Passed by value.
+struct PolyList {
+    u32 n;
+    unsigned char spos[CKKS_MAX_MODULI];
+    unsigned char dpos[CKKS_MAX_MODULI];
+    unsigned char mod[CKKS_MAX_MODULI];
+};
+
+struct ckks_key {
+    const u64* d_key;
+    u32 galois_elt;
+};
+
+struct ckks_ctx {
+    u32 log_n, N, num_q, num_p, dnum, alpha, M;
+    u32 log_lo, log_hi;  // N = 2^log_hi blocks-of-stride x 2^log_lo contiguous
+    u32 lazy_terms;      // how many products of two residues may be summed in 128 bits before a reduction
+    std::vector<u64> mod, psi;
+    std::vector<ModConst> mc;
+
+    // device tables
+    ModConst* d_mc = nullptr;         // [M]
+    u64* d_tw = nullptr;              // [M][N]  psi^bitrev(i)
+    u64* d_tw_sh = nullptr;           // Shoup companions
+    u64* d_itw = nullptr;             // [M][N]  psi^-bitrev(i)
+    u64* d_itw_sh = nullptr;
+    u64* d_modup = nullptr;           // per level, per digit: see modup_digit_stride()
+    u64* d_moddown = nullptr;         // phat_inv[k], phat_inv_sh[k], phat_q[k][num_q], pinv[num_q], pinv_sh[num_q]
+    u64* d_rescale = nullptr;         // [num_q][num_q][3]: (q_l^-1 mod q_i, its Shoup companion, q_l mod q_i)
+
+    mutable std::string err;
+
+    u32 ext_limbs(u32 level) const { return level + 1 + num_p; }
+    u32 live_digits(u32 level) const { return (level + alpha) / alpha; }
+    u32 digit_lo(u32 j) const { return j * alpha; }
+    u32 digit_hi(u32 j, u32 level) const { u32 h = (j + 1) * alpha; return h < level + 1 ? h : level + 1; }
+    u32 ext_modulus(u32 level, u32 e) const { return e <= level ? e : num_q + (e - level - 1); }
+    // ModUp table of one digit: inv[alpha], inv_sh[alpha], conv[alpha][M] (conv indexed by the
+    // position e in the extended basis of that level)
+    size_t modup_digit_stride() const { return (size_t)alpha * (2 + M); }
+    size_t modup_level_stride() const { return modup_digit_stride() * dnum; }
+    const u64* modup_table(u32 level, u32 j) const { return d_modup + level * modup_level_stride() + j * modup_digit_stride(); }
+};
+
+// ---- kernel launchers (each enqueues on `st` and returns the launch status) -------------------
+// ntt.hip
+hipError_t launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, size_t src_bstride, u64* dst,
+                      size_t dst_bstride, const PolyList& pl, u32 batch, hipStream_t st);
+// keyswitch.hip
+hipError_t launch_modup_conv(const ckks_ctx* c, u32 level, u32 j, const u64* y, const u64* c_in, u64* digit, hipStream_t st);
+hipError_t launch_key_inner(const ckks_ctx* c, u32 level, const u64* digits, const u64* key, u32 g, u64* v, hipStream_t st);
+hipError_t launch_moddown_conv(const ckks_ctx* c, u32 level, const u64* v, u64* w, hipStream_t st);
+hipError_t launch_moddown_final(const ckks_ctx* c, u32 level, const u64* v, const u64* w, const u64* add0, const u64* add1,
+                                u32 g, u64* out, hipStream_t st);
+// pointwise.hip
+hipError_t launch_automorph(const ckks_ctx* c, u32 n_polys, const u64* in, u32 g, u64* out, hipStream_t st);
+hipError_t launch_copy(const u64* in, u64* out, size_t n, hipStream_t st);
+hipError_t launch_ptct_mac(const ckks_ctx* c, u32 level, const u64* const* pts, const u64* const* cts, u32 n_terms, u64* acc,
+                           int accumulate, hipStream_t st);
+hipError_t launch_rescale_conv(const ckks_ctx* c, u32 level, const u64* r, u64* w, hipStream_t st);
+hipError_t launch_rescale_final(const ckks_ctx* c, u32 level, const u64* ct, size_t ct_cstride, const u64* w, u64* out, hipStream_t st);
+hipError_t launch_tensor(const ckks_ctx* c, u32 level, const u64* a, size_t a_cstride, const u64* b, size_t b_cstride, u64* d0,
+                         u64* d1, u64* d2, hipStream_t st);
+hipError_t launch_mask_mul(const ckks_ctx* c, u32 level, const u64* mask, const u64* ct, u64* out, hipStream_t st);
+hipError_t launch_weighted_sum(const ckks_ctx* c, u32 level, const u64* xs, u32 n_terms, const u64* w_res, u32 c_out, u64* acc,
+                               hipStream_t st);
+hipError_t launch_lincomb2(const ckks_ctx* c, u32 level, const u64* a, size_t a_cstride, const u64* ka, const u64* b,
+                           size_t b_cstride, const u64* kb, const u64* add, u64* out, hipStream_t st);

@@ -1,0 +1,157 @@
+// Hybrid (digit-decomposed) key switching for gfx950: the arithmetic behind every Rot and every
+// relinearisation (Background, "Rotations and Key Switching"; Experiments, "HE Security
+// Parameters": key switching with digits).
+//
+//   ModUp      digit j's limbs (coefficient form) -> all live q-limbs and the special primes:
+//              y_a = [c_a * (Q_j/q_a)^-1] mod q_a  in [0, q_a),
+//              d_j[t] = sum_a y_a * [Q_j/q_a]_t  mod t          (plain sum, no correction term)
+//   inner      v_comp[t] = sum_j sigma_g(d_j)[t] * key[j][comp][t]   (sigma_g = gather, g = 1: none)
+//   ModDown    z_a = [v_{p_a} * (P/p_a)^-1] mod p_a,  w[i] = sum_a z_a * [P/p_a]_{q_i}  (coefficient
+//              form), then in NTT form u[i] = (v[q_i] - w[i]) * P^-1  (+ an optional addend)
+// Sums of products are accumulated unreduced in 128 bits and reduced once.
+#include "ctx.h"
+
+#define KS_THREADS 256
+#define KS_MAX_DIGIT 16  // limbs per digit / special primes handled in registers
+
+__device__ __forceinline__ u32 galois_gather_index(u32 k, u32 g, u32 log_n) {
+    // evaluation point of entry k is psi^(2*brv(k)+1); sigma_g reads the entry whose point is that
+    // power times g
+    u32 e = ((2u * (__brev(k) >> (32 - log_n)) + 1u) * g) & ((2u << log_n) - 1u);
+    return __brev((e - 1u) >> 1) >> (32 - log_n);
+}
+
+// ---- ModUp: basis extension of one digit --------------------------------------------------------
+// y     [nd][N]      digit limbs in coefficient form (canonical)
+// c_in  [level+1][N] the polynomial being switched, NTT form (source of the digit's own limbs)
+// digit [E][N]       out: own limbs copied (NTT form), other limbs in coefficient form
+#define MODUP_LIMBS_PER_BLOCK 4
+__global__ __launch_bounds__(KS_THREADS) void modup_conv_kernel(const u64* __restrict__ y, const u64* __restrict__ c_in,
+                                                                u64* __restrict__ digit, const u64* __restrict__ tab,
+                                                                const ModConst* __restrict__ mc, u32 N, u32 level, u32 num_q,
+                                                                u32 lo, u32 nd, u32 alpha, u32 M, u32 E) {
+    const u32 x = blockIdx.x * KS_THREADS + threadIdx.x;
+    if (x >= N) return;
+    u64 yv[KS_MAX_DIGIT];
+#pragma unroll
+    for (u32 a = 0; a < KS_MAX_DIGIT; a++)
+        if (a < nd) yv[a] = mul_shoup(y[(size_t)a * N + x], tab[a], tab[alpha + a], mc[lo + a].q);
+    const u32 e0 = blockIdx.y * MODUP_LIMBS_PER_BLOCK;
+    for (u32 e = e0; e < e0 + MODUP_LIMBS_PER_BLOCK && e < E; e++) {
+        const u32 t = e <= level ? e : num_q + (e - level - 1);
+        if (t >= lo && t < lo + nd) {
+            digit[(size_t)e * N + x] = c_in[(size_t)t * N + x];
+            continue;
+        }
+        U128 acc = {0, 0};
+#pragma unroll
+        for (u32 a = 0; a < KS_MAX_DIGIT; a++)
+            if (a < nd) acc_wide(acc, yv[a], tab[2 * alpha + (size_t)a * M + e]);
+        digit[(size_t)e * N + x] = barrett_reduce(acc, mc[t]);
+    }
+}
+
+hipError_t launch_modup_conv(const ckks_ctx* c, u32 level, u32 j, const u64* y, const u64* c_in, u64* digit, hipStream_t st) {
+    const u32 E = c->ext_limbs(level), lo = c->digit_lo(j), nd = c->digit_hi(j, level) - lo;
+    dim3 grid((c->N + KS_THREADS - 1) / KS_THREADS, (E + MODUP_LIMBS_PER_BLOCK - 1) / MODUP_LIMBS_PER_BLOCK);
+    hipLaunchKernelGGL(modup_conv_kernel, grid, dim3(KS_THREADS), 0, st, y, c_in, digit, c->modup_table(level, j), c->d_mc,
+                       c->N, level, c->num_q, lo, nd, c->alpha, c->M, E);
+    return hipGetLastError();
+}
+
+// ---- inner product with the switching key ------------------------------------------------------
+// digits [beta][E][N], key [dnum][2][M][N], v [2][E][N]
+__global__ __launch_bounds__(KS_THREADS) void key_inner_kernel(const u64* __restrict__ digits, const u64* __restrict__ key,
+                                                               u64* __restrict__ v, const ModConst* __restrict__ mc, u32 log_n,
+                                                               u32 level, u32 num_q, u32 M, u32 E, u32 beta, u32 g) {
+    const u32 N = 1u << log_n;
+    const u32 x = blockIdx.x * KS_THREADS + threadIdx.x;
+    if (x >= N) return;
+    const u32 e = blockIdx.y;
+    const u32 t = e <= level ? e : num_q + (e - level - 1);
+    const u32 xs = g == 1 ? x : galois_gather_index(x, g, log_n);
+    U128 acc0 = {0, 0}, acc1 = {0, 0};
+    const ModConst m = mc[t];
+    for (u32 j = 0; j < beta; j++) {
+        const u64 d = digits[((size_t)j * E + e) * N + xs];
+        acc_wide(acc0, d, key[(((size_t)j * 2 + 0) * M + t) * N + x]);
+        acc_wide(acc1, d, key[(((size_t)j * 2 + 1) * M + t) * N + x]);
+        if ((j & 15) == 15) {  // keep the unreduced sums inside the Barrett input range
+            acc0.lo = barrett_reduce(acc0, m); acc0.hi = 0;
+            acc1.lo = barrett_reduce(acc1, m); acc1.hi = 0;
+        }
+    }
+    v[((size_t)0 * E + e) * N + x] = barrett_reduce(acc0, m);
+    v[((size_t)1 * E + e) * N + x] = barrett_reduce(acc1, m);
+}
+
+hipError_t launch_key_inner(const ckks_ctx* c, u32 level, const u64* digits, const u64* key, u32 g, u64* v, hipStream_t st) {
+    const u32 E = c->ext_limbs(level);
+    dim3 grid((c->N + KS_THREADS - 1) / KS_THREADS, E);
+    hipLaunchKernelGGL(key_inner_kernel, grid, dim3(KS_THREADS), 0, st, digits, key, v, c->d_mc, c->log_n, level, c->num_q,
+                       c->M, E, c->live_digits(level), g);
+    return hipGetLastError();
+}
+
+// ---- ModDown, conversion of the P-part ----------------------------------------------------------
+// v [2][E][N]: limbs level+1.. hold the P-part in coefficient form.  w [2][level+1][N] (coefficients)
+#define MODDOWN_LIMBS_PER_BLOCK 4
+__global__ __launch_bounds__(KS_THREADS) void moddown_conv_kernel(const u64* __restrict__ v, u64* __restrict__ w,
+                                                                  const u64* __restrict__ tab, const ModConst* __restrict__ mc,
+                                                                  u32 N, u32 level, u32 num_q, u32 k, u32 E) {
+    const u32 x = blockIdx.x * KS_THREADS + threadIdx.x;
+    if (x >= N) return;
+    const u32 comp = blockIdx.z;
+    u64 z[KS_MAX_DIGIT];
+#pragma unroll
+    for (u32 a = 0; a < KS_MAX_DIGIT; a++)
+        if (a < k) z[a] = mul_shoup(v[((size_t)comp * E + level + 1 + a) * N + x], tab[a], tab[k + a], mc[num_q + a].q);
+    const u64* phat_q = tab + 2 * k;  // [k][num_q]
+    const u32 i0 = blockIdx.y * MODDOWN_LIMBS_PER_BLOCK;
+    for (u32 i = i0; i < i0 + MODDOWN_LIMBS_PER_BLOCK && i <= level; i++) {
+        U128 acc = {0, 0};
+#pragma unroll
+        for (u32 a = 0; a < KS_MAX_DIGIT; a++)
+            if (a < k) acc_wide(acc, z[a], phat_q[(size_t)a * num_q + i]);
+        w[((size_t)comp * (level + 1) + i) * N + x] = barrett_reduce(acc, mc[i]);
+    }
+}
+
+hipError_t launch_moddown_conv(const ckks_ctx* c, u32 level, const u64* v, u64* w, hipStream_t st) {
+    dim3 grid((c->N + KS_THREADS - 1) / KS_THREADS, (level + 1 + MODDOWN_LIMBS_PER_BLOCK - 1) / MODDOWN_LIMBS_PER_BLOCK, 2);
+    hipLaunchKernelGGL(moddown_conv_kernel, grid, dim3(KS_THREADS), 0, st, v, w, c->d_moddown, c->d_mc, c->N, level,
+                       c->num_q, c->num_p, c->ext_limbs(level));
+    return hipGetLastError();
+}
+
+// ---- ModDown, last step: out[comp][i] = (v[comp][i] - w[comp][i]) * P^-1 (+ addend) --------------
+// add0 / add1: optional polynomials [level+1][N] added to component 0 / 1; when g != 1 the addend
+// is read through the sigma_g gather (Rot: c0' = sigma_g(c0) + u0).
+__global__ __launch_bounds__(KS_THREADS) void moddown_final_kernel(const u64* __restrict__ v, const u64* __restrict__ w,
+                                                                   const u64* __restrict__ add0, const u64* __restrict__ add1,
+                                                                   u64* __restrict__ out, const u64* __restrict__ tab,
+                                                                   const ModConst* __restrict__ mc, u32 log_n, u32 level,
+                                                                   u32 num_q, u32 k, u32 E, u32 g) {
+    const u32 N = 1u << log_n;
+    const u32 x = blockIdx.x * KS_THREADS + threadIdx.x;
+    if (x >= N) return;
+    const u32 i = blockIdx.y, comp = blockIdx.z;
+    const u64 q = mc[i].q;
+    const u64* pinv = tab + 2 * k + (size_t)k * num_q;
+    u64 d = sub_mod(v[((size_t)comp * E + i) * N + x], w[((size_t)comp * (level + 1) + i) * N + x], q);
+    u64 r = mul_shoup(d, pinv[i], pinv[num_q + i], q);
+    const u64* add = comp == 0 ? add0 : add1;
+    if (add) {
+        const u32 xs = g == 1 ? x : galois_gather_index(x, g, log_n);
+        r = add_mod(r, add[(size_t)i * N + xs], q);
+    }
+    out[((size_t)comp * (level + 1) + i) * N + x] = r;
+}
+
+hipError_t launch_moddown_final(const ckks_ctx* c, u32 level, const u64* v, const u64* w, const u64* add0, const u64* add1,
+                                u32 g, u64* out, hipStream_t st) {
+    dim3 grid((c->N + KS_THREADS - 1) / KS_THREADS, level + 1, 2);
+    hipLaunchKernelGGL(moddown_final_kernel, grid, dim3(KS_THREADS), 0, st, v, w, add0, add1, out, c->d_moddown, c->d_mc,
+                       c->log_n, level, c->num_q, c->num_p, c->ext_limbs(level), g);
+    return hipGetLastError();
+}

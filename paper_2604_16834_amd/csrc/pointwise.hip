@@ -1,0 +1,243 @@
+// Pointwise (per evaluation point) kernels on limb-major ciphertexts for gfx950: automorphism
+// gather, plaintext-ciphertext multiply-accumulate (Methodology, "Convolution Evaluation", Eq. 11
+// and the rotation-free channel sum), the two elementwise steps of rescaling, the tensor product
+// of a ciphertext multiplication and small linear combinations for the polynomial activation
+// ("Other Layers").  All of them stream HBM once; coefficients x are the fastest index so every
+// wavefront touches contiguous 512-byte runs.
+#include "ctx.h"
+
+#define PW_THREADS 256
+
+__device__ __forceinline__ u32 pw_gather_index(u32 k, u32 g, u32 log_n) {
+    u32 e = ((2u * (__brev(k) >> (32 - log_n)) + 1u) * g) & ((2u << log_n) - 1u);
+    return __brev((e - 1u) >> 1) >> (32 - log_n);
+}
+
+// out[p][k] = in[p][pi_g(k)] for n_polys limb-polys (the same gather for every modulus)
+__global__ __launch_bounds__(PW_THREADS) void automorph_kernel(const u64* __restrict__ in, u64* __restrict__ out, u32 log_n, u32 g) {
+    const u32 N = 1u << log_n;
+    const u32 x = blockIdx.x * PW_THREADS + threadIdx.x;
+    if (x >= N) return;
+    const size_t base = (size_t)blockIdx.y * N;
+    out[base + x] = in[base + pw_gather_index(x, g, log_n)];
+}
+
+hipError_t launch_automorph(const ckks_ctx* c, u32 n_polys, const u64* in, u32 g, u64* out, hipStream_t st) {
+    dim3 grid((c->N + PW_THREADS - 1) / PW_THREADS, n_polys);
+    hipLaunchKernelGGL(automorph_kernel, grid, dim3(PW_THREADS), 0, st, in, out, c->log_n, g);
+    return hipGetLastError();
+}
+
+__global__ __launch_bounds__(PW_THREADS) void copy_kernel(const u64* __restrict__ in, u64* __restrict__ out, size_t n) {
+    size_t i = (size_t)blockIdx.x * PW_THREADS + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * PW_THREADS;
+    for (; i < n; i += stride) out[i] = in[i];
+}
+
+hipError_t launch_copy(const u64* in, u64* out, size_t n, hipStream_t st) {
+    if (n == 0) return hipSuccess;
+    size_t blocks = (n + PW_THREADS - 1) / PW_THREADS;
+    if (blocks > 16384) blocks = 16384;
+    hipLaunchKernelGGL(copy_kernel, dim3((u32)blocks), dim3(PW_THREADS), 0, st, in, out, n);
+    return hipGetLastError();
+}
+
+// ---- plaintext x ciphertext multiply-accumulate -------------------------------------------------
+#define MAC_TERMS_PER_LAUNCH 16
+struct MacTerms {
+    const u64* pt[MAC_TERMS_PER_LAUNCH];
+    const u64* ct[MAC_TERMS_PER_LAUNCH];
+    u32 n;
+};
+
+__global__ __launch_bounds__(PW_THREADS) void ptct_mac_kernel(MacTerms T, u64* __restrict__ acc, const ModConst* __restrict__ mc,
+                                                              u32 N, u32 level, int accumulate) {
+    const u32 x = blockIdx.x * PW_THREADS + threadIdx.x;
+    if (x >= N) return;
+    const u32 i = blockIdx.y, comp = blockIdx.z;
+    const ModConst m = mc[i];
+    const size_t po = (size_t)i * N + x, co = ((size_t)comp * (level + 1) + i) * N + x;
+    U128 s = {0, 0};
+    if (accumulate) s.lo = acc[co];
+    for (u32 k = 0; k < T.n; k++) acc_wide(s, T.pt[k][po], T.ct[k][co]);
+    acc[co] = barrett_reduce(s, m);
+}
+
+hipError_t launch_ptct_mac(const ckks_ctx* c, u32 level, const u64* const* pts, const u64* const* cts, u32 n_terms, u64* acc,
+                           int accumulate, hipStream_t st) {
+    dim3 grid((c->N + PW_THREADS - 1) / PW_THREADS, level + 1, 2);
+    for (u32 k0 = 0; k0 < n_terms; k0 += MAC_TERMS_PER_LAUNCH) {
+        MacTerms T;
+        T.n = n_terms - k0 < MAC_TERMS_PER_LAUNCH ? n_terms - k0 : MAC_TERMS_PER_LAUNCH;
+        for (u32 k = 0; k < MAC_TERMS_PER_LAUNCH; k++) {
+            T.pt[k] = k < T.n ? pts[k0 + k] : nullptr;
+            T.ct[k] = k < T.n ? cts[k0 + k] : nullptr;
+        }
+        hipLaunchKernelGGL(ptct_mac_kernel, grid, dim3(PW_THREADS), 0, st, T, acc, c->d_mc, c->N, level, accumulate || k0 > 0);
+    }
+    return hipGetLastError();
+}
+
+// ---- rescale ------------------------------------------------------------------------------------
+// r [2][N]: dropped limb of both components in coefficient form.  w[comp][i][x] = centred r mod q_i.
+__global__ __launch_bounds__(PW_THREADS) void rescale_conv_kernel(const u64* __restrict__ r, u64* __restrict__ w,
+                                                                  const u64* __restrict__ tab, const ModConst* __restrict__ mc,
+                                                                  u32 N, u32 level, u32 num_q) {
+    const u32 x = blockIdx.x * PW_THREADS + threadIdx.x;
+    if (x >= N) return;
+    const u32 i = blockIdx.y, comp = blockIdx.z;
+    const ModConst m = mc[i];
+    const u64 ql = mc[level].q;
+    const u64 rv = r[(size_t)comp * N + x];
+    u64 v = reduce_word(rv, m);
+    if (rv > ql / 2) v = sub_mod(v, tab[((size_t)level * num_q + i) * 3 + 2], m.q);  // r - q_l
+    w[((size_t)comp * level + i) * N + x] = v;
+}
+
+hipError_t launch_rescale_conv(const ckks_ctx* c, u32 level, const u64* r, u64* w, hipStream_t st) {
+    dim3 grid((c->N + PW_THREADS - 1) / PW_THREADS, level, 2);
+    hipLaunchKernelGGL(rescale_conv_kernel, grid, dim3(PW_THREADS), 0, st, r, w, c->d_rescale, c->d_mc, c->N, level, c->num_q);
+    return hipGetLastError();
+}
+
+// out[comp][i] = (ct[comp][i] - w[comp][i]) * q_l^-1, i < level; ct has component stride ct_cstride
+__global__ __launch_bounds__(PW_THREADS) void rescale_final_kernel(const u64* __restrict__ ct, size_t ct_cstride,
+                                                                   const u64* __restrict__ w, u64* __restrict__ out,
+                                                                   const u64* __restrict__ tab, const ModConst* __restrict__ mc,
+                                                                   u32 N, u32 level, u32 num_q) {
+    const u32 x = blockIdx.x * PW_THREADS + threadIdx.x;
+    if (x >= N) return;
+    const u32 i = blockIdx.y, comp = blockIdx.z;
+    const u64 q = mc[i].q;
+    const u64* t = tab + ((size_t)level * num_q + i) * 3;
+    const size_t o = ((size_t)comp * level + i) * N + x;
+    u64 d = sub_mod(ct[comp * ct_cstride + (size_t)i * N + x], w[o], q);
+    out[o] = mul_shoup(d, t[0], t[1], q);
+}
+
+hipError_t launch_rescale_final(const ckks_ctx* c, u32 level, const u64* ct, size_t ct_cstride, const u64* w, u64* out, hipStream_t st) {
+    dim3 grid((c->N + PW_THREADS - 1) / PW_THREADS, level, 2);
+    hipLaunchKernelGGL(rescale_final_kernel, grid, dim3(PW_THREADS), 0, st, ct, ct_cstride, w, out, c->d_rescale, c->d_mc, c->N,
+                       level, c->num_q);
+    return hipGetLastError();
+}
+
+// ---- tensor product of two ciphertexts ----------------------------------------------------------
+// d0 = a0 b0, d1 = a0 b1 + a1 b0, d2 = a1 b1 on limbs 0..level; operands may sit at a higher level
+// (component strides a_cstride, b_cstride in elements)
+__global__ __launch_bounds__(PW_THREADS) void tensor_kernel(const u64* __restrict__ a, size_t a_cstride, const u64* __restrict__ b,
+                                                            size_t b_cstride, u64* __restrict__ d0, u64* __restrict__ d1,
+                                                            u64* __restrict__ d2, const ModConst* __restrict__ mc, u32 N) {
+    const u32 x = blockIdx.x * PW_THREADS + threadIdx.x;
+    if (x >= N) return;
+    const u32 i = blockIdx.y;
+    const ModConst m = mc[i];
+    const size_t o = (size_t)i * N + x;
+    const u64 a0 = a[o], a1 = a[a_cstride + o], b0 = b[o], b1 = b[b_cstride + o];
+    d0[o] = mulmod_barrett(a0, b0, m);
+    U128 s = mul_wide(a0, b1);
+    acc_wide(s, a1, b0);
+    d1[o] = barrett_reduce(s, m);
+    d2[o] = mulmod_barrett(a1, b1, m);
+}
+
+hipError_t launch_tensor(const ckks_ctx* c, u32 level, const u64* a, size_t a_cstride, const u64* b, size_t b_cstride, u64* d0,
+                         u64* d1, u64* d2, hipStream_t st) {
+    dim3 grid((c->N + PW_THREADS - 1) / PW_THREADS, level + 1);
+    hipLaunchKernelGGL(tensor_kernel, grid, dim3(PW_THREADS), 0, st, a, a_cstride, b, b_cstride, d0, d1, d2, c->d_mc, c->N);
+    return hipGetLastError();
+}
+
+// ---- convolution operands -----------------------------------------------------------------------
+// out[comp][i] = mask[i] * ct[comp][i]: an aligned ciphertext times the tap's encoded validity mask
+__global__ __launch_bounds__(PW_THREADS) void mask_mul_kernel(const u64* __restrict__ mask, const u64* __restrict__ ct,
+                                                              u64* __restrict__ out, const ModConst* __restrict__ mc, u32 N, u32 level) {
+    const u32 x = blockIdx.x * PW_THREADS + threadIdx.x;
+    if (x >= N) return;
+    const u32 i = blockIdx.y, comp = blockIdx.z;
+    const size_t co = ((size_t)comp * (level + 1) + i) * N + x;
+    out[co] = mulmod_barrett(mask[(size_t)i * N + x], ct[co], mc[i]);
+}
+
+hipError_t launch_mask_mul(const ckks_ctx* c, u32 level, const u64* mask, const u64* ct, u64* out, hipStream_t st) {
+    dim3 grid((c->N + PW_THREADS - 1) / PW_THREADS, level + 1, 2);
+    hipLaunchKernelGGL(mask_mul_kernel, grid, dim3(PW_THREADS), 0, st, mask, ct, out, c->d_mc, c->N, level);
+    return hipGetLastError();
+}
+
+// acc[o][comp][i][x] = sum_k w_res[o][k][i] * xs[k][comp][i][x]  mod q_i: the sum over (input
+// channel, tap) of Eq. 11 with the integer weight factored out of the plaintext.  Each thread keeps
+// WS_OUT_TILE output channels' 128-bit sums so that every xs element is loaded once per tile.
+#define WS_OUT_TILE 4
+__global__ __launch_bounds__(PW_THREADS) void weighted_sum_kernel(const u64* __restrict__ xs, const u64* __restrict__ w_res,
+                                                                  u64* __restrict__ acc, const ModConst* __restrict__ mc, u32 N,
+                                                                  u32 level, u32 n_terms, u32 c_out, u32 lazy_terms) {
+    const u32 x = blockIdx.x * PW_THREADS + threadIdx.x;
+    if (x >= N) return;
+    const u32 L1 = level + 1;
+    const u32 i = blockIdx.y % L1, comp = blockIdx.y / L1;
+    const u32 o0 = blockIdx.z * WS_OUT_TILE;
+    const ModConst m = mc[i];
+    const size_t ct_stride = (size_t)2 * L1 * N;
+    const size_t off = ((size_t)comp * L1 + i) * N + x;
+    U128 s[WS_OUT_TILE];
+#pragma unroll
+    for (u32 t = 0; t < WS_OUT_TILE; t++) s[t] = {0, 0};
+    u32 pending = 0;
+    for (u32 k = 0; k < n_terms; k++) {
+        const u64 v = xs[k * ct_stride + off];
+#pragma unroll
+        for (u32 t = 0; t < WS_OUT_TILE; t++)
+            if (o0 + t < c_out) acc_wide(s[t], v, w_res[((size_t)(o0 + t) * n_terms + k) * L1 + i]);
+        if (++pending == lazy_terms) {
+            pending = 0;
+#pragma unroll
+            for (u32 t = 0; t < WS_OUT_TILE; t++) { s[t].lo = barrett_reduce(s[t], m); s[t].hi = 0; }
+        }
+    }
+#pragma unroll
+    for (u32 t = 0; t < WS_OUT_TILE; t++)
+        if (o0 + t < c_out) acc[(o0 + t) * ct_stride + off] = barrett_reduce(s[t], m);
+}
+
+hipError_t launch_weighted_sum(const ckks_ctx* c, u32 level, const u64* xs, u32 n_terms, const u64* w_res, u32 c_out, u64* acc,
+                               hipStream_t st) {
+    dim3 grid((c->N + PW_THREADS - 1) / PW_THREADS, 2 * (level + 1), (c_out + WS_OUT_TILE - 1) / WS_OUT_TILE);
+    hipLaunchKernelGGL(weighted_sum_kernel, grid, dim3(PW_THREADS), 0, st, xs, w_res, acc, c->d_mc, c->N, level, n_terms, c_out,
+                       c->lazy_terms);
+    return hipGetLastError();
+}
+
+// ---- out = ka * a + kb * b (+ add) on limbs 0..level, integer scalars given by residues ---------
+struct Scalars {
+    u64 ka[CKKS_MAX_MODULI];
+    u64 kb[CKKS_MAX_MODULI];
+};
+
+__global__ __launch_bounds__(PW_THREADS) void lincomb2_kernel(const u64* __restrict__ a, size_t a_cstride, const u64* __restrict__ b,
+                                                              size_t b_cstride, const u64* __restrict__ add, Scalars K,
+                                                              u64* __restrict__ out, const ModConst* __restrict__ mc, u32 N, u32 level) {
+    const u32 x = blockIdx.x * PW_THREADS + threadIdx.x;
+    if (x >= N) return;
+    const u32 i = blockIdx.y, comp = blockIdx.z;
+    const ModConst m = mc[i];
+    const size_t o = (size_t)i * N + x;
+    U128 s = mul_wide(a[comp * a_cstride + o], K.ka[i]);
+    acc_wide(s, b[comp * b_cstride + o], K.kb[i]);
+    const size_t oo = ((size_t)comp * (level + 1) + i) * N + x;
+    u64 r = barrett_reduce(s, m);
+    if (add) r = add_mod(r, add[oo], m.q);
+    out[oo] = r;
+}
+
+hipError_t launch_lincomb2(const ckks_ctx* c, u32 level, const u64* a, size_t a_cstride, const u64* ka, const u64* b,
+                           size_t b_cstride, const u64* kb, const u64* add, u64* out, hipStream_t st) {
+    Scalars K;
+    for (u32 i = 0; i < CKKS_MAX_MODULI; i++) {
+        K.ka[i] = i <= level ? ka[i] : 0;
+        K.kb[i] = i <= level ? kb[i] : 0;
+    }
+    dim3 grid((c->N + PW_THREADS - 1) / PW_THREADS, level + 1, 2);
+    hipLaunchKernelGGL(lincomb2_kernel, grid, dim3(PW_THREADS), 0, st, a, a_cstride, b, b_cstride, add, K, out, c->d_mc, c->N, level);
+    return hipGetLastError();
+}
