@@ -1,0 +1,200 @@
+#!/usr/bin/env python3
+"""Benchmark of the whole hot path on one MI355X.
+
+One step = one pass of the batched ResNet-20 stage-3 block slice over one batch of synthetic input
+(workload cfg5_resnet20_stage3: N = 2^16, 24 ciphertext limbs + 8 special primes, dnum 3, 64 -> 64
+channels, 3x3 convolution on 8x8 images, batch 512 = 32768 slots per channel ciphertext), i.e.
+he_conv_batched (64 shared decompositions, 512 hoisted rotations, the 64x576 multiply-accumulate,
+64 rescales) followed by the degree-7 polynomial activation on every output channel (256
+ciphertext products with relinearisation, 320 rescales).  All inputs are resident in HBM before
+the timed region.  Prints ONE JSON line.
+
+Inputs are seeded uniform residues of the right shapes (ciphertexts, switching keys, mask
+plaintexts, integer weights): modular arithmetic has no data-dependent control flow, so timing does
+not depend on the values; correctness on real ciphertexts is what the parity tests establish.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+# vector integer peak: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3e12 32-bit lane-operations/s;
+# one 64-bit modular multiply-add costs about 14 of them, so ~2.8e12 modmul/s
+ALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
+LANE_OPS_PER_MODMUL = 14.0
+HBM_KERNELS = {"key_inner", "moddown_final", "mask_mul", "tensor", "lincomb2", "rescale_final", "rescale_conv",
+               "automorph", "ptct_mac", "ntt_fwd_hi", "ntt_fwd_lo", "ntt_inv_lo", "ntt_inv_hi", "moddown_conv", "modup_conv"}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="cfg5_resnet20_stage3")
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
+    ap.add_argument("--no-kernel-timing", action="store_true", help="skip the per-kernel event pass")
+    return ap.parse_args()
+
+
+def cpu_baseline(wl, params):
+    """Times the CPU oracle on a bounded sample of the same workload and extrapolates to one step."""
+    import numpy as np
+    from oracle import Oracle
+    from workloads import conv_tap_offsets, uniform_residues
+    orc = Oracle(params)
+    level = params.num_q - 1
+    q = params.moduli
+    rng_ct = uniform_residues((2, level + 1, orc.N), q[:level + 1], "cpu_ct")
+    key = uniform_residues((params.dnum, 2, orc.M, orc.N), q, "cpu_key")
+    offs = [o for o in conv_tap_offsets(wl.width) if o]
+    t0 = time.perf_counter()
+    digits = orc.modup(rng_ct[1], level)
+    aligned = [orc.rotate(rng_ct, level, o, key, True, digits) for o in offs]
+    t_align = time.perf_counter() - t0                      # one input channel: 1 ModUp + 8 rotations
+    pts = [uniform_residues((level + 1, orc.N), q[:level + 1], "cpu_pt%d" % i) for i in range(9)]
+    t0 = time.perf_counter()
+    acc = orc.ptct_mac(pts, aligned + [rng_ct], level)
+    t_mac = time.perf_counter() - t0                        # 9 taps of one (input, output) channel pair
+    t0 = time.perf_counter()
+    x = orc.rescale(acc, level)
+    t_resc = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    orc.poly_activation(x, level - 1, (3 << 40, -(5 << 40), 7 << 40, -(9 << 40)), key)
+    t_act = time.perf_counter() - t0
+    step = wl.c_in * t_align + wl.c_in * wl.c_out * t_mac + wl.c_out * (t_resc + t_act)
+    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    return {
+        "value": step * 1e3 / wl.batch, "unit": "ms/image", "cores": cores, "kind": "oracle",
+        "sample": ("oracle timed on one input channel's alignment (1 ModUp + 8 hoisted rotations, %.2f s), one 9-tap "
+                   "multiply-accumulate (%.2f s), one rescale (%.2f s) and one degree-7 activation (%.2f s) at full "
+                   "size, extrapolated to %d alignments, %d 9-tap MACs, %d rescales and activations"
+                   % (t_align, t_mac, t_resc, t_act, wl.c_in, wl.c_in * wl.c_out, wl.c_out)),
+        "step_seconds_extrapolated": step,
+    }
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    import paper_2604_16834_amd as hx
+    from workloads import CONFIGS, conv_tap_offsets, uniform_residues
+
+    wl = CONFIGS[args.workload]
+    params = wl.params()
+    ctx = hx.Context(params)
+    N, level, q = params.n, params.num_q - 1, params.moduli
+    M = params.num_q + params.num_p
+    t_setup = time.perf_counter()
+    ins = [hx.from_host(uniform_residues((2, level + 1, N), q[:level + 1], "in%d" % c)) for c in range(wl.c_in)]
+    offs = conv_tap_offsets(wl.width)
+    keys = [hx.ckks_key_load(ctx, hx.from_host(uniform_residues((params.dnum, 2, M, N), q, "rk%d" % t)),
+                             hx.ckks_galois_element(ctx, off)) if off else None for t, off in enumerate(offs)]
+    rlk = hx.ckks_key_load(ctx, hx.from_host(uniform_residues((params.dnum, 2, M, N), q, "rlk")), 0)
+    masks = hx.from_host(uniform_residues((9, level + 1, N), q[:level + 1], "masks"))
+    w_res = hx.from_host(uniform_residues((wl.c_out * wl.c_in * 9, level + 1, 1), q[:level + 1], "w").reshape(wl.c_out, wl.c_in, 9, level + 1))
+    conv_out = [hx.empty(2, level, N) for _ in range(wl.c_out)]
+    act_out = [hx.empty(2, level - 4, N) for _ in range(wl.c_out)]
+    k_act = (3 << 40, -(5 << 40), 7 << 40, -(9 << 40))
+    ws_bytes = max(hx.he_conv_workspace_bytes(ctx, wl.c_in, wl.c_out, wl.height, wl.width, wl.batch, level),
+                   hx.ckks_workspace_bytes(ctx, hx.binding.CKKS_OP_POLY_ACT, level - 1))
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    print("[bench] setup %.1f s, workspace %.2f GiB" % (time.perf_counter() - t_setup, ws_bytes / 2**30), file=sys.stderr, flush=True)
+
+    def step():
+        hx.he_conv_batched(ctx, wl.height, wl.width, wl.batch, level, ins, keys, masks, w_res, wl.c_out, outs=conv_out, ws=ws)
+        for o in range(wl.c_out):
+            hx.he_poly_act_deg7(ctx, conv_out[o], level - 1, k_act, rlk, out=act_out[o], ws=ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+    print("[bench] %d steps, %.2f ms/step" % (args.steps, ms_per_step), file=sys.stderr, flush=True)
+
+    n_rot = wl.c_in * 8
+    n_keyswitch = n_rot + 4 * wl.c_out
+    result = {
+        "metric": "keyswitch rotations/s + amortised HE-conv ms/image at N=2^16; % peak HBM GB/s",
+        "value": ms_per_step / wl.batch,
+        "unit": "ms/image (amortised, conv 64->64 3x3 + degree-7 activation, batch 512)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u64", "data": "synthetic",
+        "config": {"workload": wl.name, "log_n": params.log_n, "limbs": params.num_q, "special_primes": params.num_p,
+                   "dnum": params.dnum, "c_in": wl.c_in, "c_out": wl.c_out, "image": "%dx%d" % (wl.height, wl.width),
+                   "batch": wl.batch, "rotations_per_step": n_rot, "keyswitches_per_step": n_keyswitch},
+    }
+
+    # per-kernel event timing over one more step (every launch bracketed on its own stream)
+    if not args.no_kernel_timing:
+        hx.ckks_prof_begin(ctx, None, max_launches=1 << 16)
+        step()
+        prof = hx.ckks_prof_end(ctx)
+        dropped = prof.pop("dropped")
+        total = sum(v["ms"] for v in prof.values())
+        kernels = {}
+        for name, v in sorted(prof.items(), key=lambda kv: -kv[1]["ms"]):
+            kernels[name] = {"ms": round(v["ms"], 3), "launches": v["launches"], "avg_us": round(1e3 * v["ms"] / v["launches"], 2),
+                             "GB/s": round(v["bytes"] / v["ms"] / 1e6, 1), "Gmodmul/s": round(v["ops"] / v["ms"] / 1e6, 1)}
+        result["kernels"] = kernels
+        result["kernel_ms_total"] = round(total, 2)
+        result["kernel_events_dropped"] = dropped
+        dom = next(iter(kernels))
+        v = prof[dom]
+        if dom == "weighted_sum":
+            peak = ALU_PEAK_LANE_OPS / LANE_OPS_PER_MODMUL / 1e12
+            ach = v["ops"] / (v["ms"] * 1e-3) / 1e12
+            result["roofline"] = {"kernel": dom, "bound": "alu", "achieved": ach, "peak": peak, "unit": "Tmodmul/s",
+                                  "frac": ach / peak, "traffic": None}
+        else:
+            ach = v["bytes"] / (v["ms"] * 1e-3) / 1e9
+            result["roofline"] = {"kernel": dom, "bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                  "frac": ach / HBM_PEAK_GBS, "traffic": None}
+        ki = prof.get("key_inner")
+        if ki:
+            ach = ki["bytes"] / (ki["ms"] * 1e-3) / 1e9
+            result["key_inner_hbm"] = {"achieved_GBs": ach, "frac_of_peak": ach / HBM_PEAK_GBS, "avg_us": 1e3 * ki["ms"] / ki["launches"]}
+
+    # rotations/s on the rotation microbenchmark shape of this parameter set: 8 hoisted rotations of one ciphertext
+    rot_outs = [hx.empty(2, level + 1, N) for _ in range(8)]
+    rot_offs = [o for o in offs if o]
+    rot_keys = [k for k in keys if k is not None]
+    for hoisted in (True, False):
+        hx.ckks_rotate_hoisted(ctx, ins[0], level, rot_offs, rot_keys, hoisted, outs=rot_outs, ws=ws)
+        torch.cuda.synchronize()
+        reps = 8
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            hx.ckks_rotate_hoisted(ctx, ins[0], level, rot_offs, rot_keys, hoisted, outs=rot_outs, ws=ws)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        result["rotations_per_s_%s" % ("hoisted" if hoisted else "unhoisted")] = 8 * reps / dt
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(wl, params)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

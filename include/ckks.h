@@ -102,8 +102,9 @@ uint32_t ckks_galois_element(const ckks_ctx* ctx, int32_t offset);
 /* Hybrid key switch of one polynomial (Background, "Rotations and Key Switching"):
  * d_c uint64[level+1][N] -> d_out uint64[2][level+1][N] with out0 + out1*s = c*s' + small noise,
  * s' the secret the key was made for.  Steps: per digit iNTT and basis extension to the live
- * q-limbs and the special primes (plain, uncorrected sum), NTT, inner product with the key,
- * division by P (floor-like, uncorrected). */
+ * q-limbs and the special primes (centred representatives, plain sum without floating-point
+ * correction), NTT, inner product with the key, division by P (P-part extended the same way, so
+ * the division rounds to nearest up to an error below num_p/2). */
 int ckks_keyswitch(const ckks_ctx* ctx, const uint64_t* d_c, uint32_t level, const ckks_key* key,
                    uint64_t* d_out, void* d_ws, size_t ws_bytes, void* stream);
 
@@ -112,7 +113,7 @@ int ckks_keyswitch(const ckks_ctx* ctx, const uint64_t* d_c, uint32_t level, con
  * an offset that is 0 mod N/2 is a plain copy and needs no key (keys[t] may be NULL).
  * hoisted = 1: c1 is decomposed and extended once and every rotation permutes the extended digits
  * ("fast rotations"); hoisted = 0: each rotation permutes the ciphertext and key-switches the
- * permuted c1.  The two orders give different residues that decrypt to the same slots up to noise.
+ * permuted c1.  Both orders give the same residues (centred digits commute with the automorphism).
  * h_d_outs: host array of n_rot device pointers, each uint64[2][level+1][N]. */
 int ckks_rotate_hoisted(const ckks_ctx* ctx, const uint64_t* d_ct, uint32_t level,
                         const int32_t* h_offsets, uint32_t n_rot, const ckks_key* const* keys,
@@ -168,6 +169,20 @@ int he_conv_batched(const ckks_ctx* ctx, const he_conv_desc* desc, const uint64_
  * tracks scales).  d_x uint64[2][level+1][N], level >= 4  ->  d_out uint64[2][level-3][N]. */
 int he_poly_act_deg7(const ckks_ctx* ctx, const uint64_t* d_x, uint32_t level, const int64_t* h_k,
                      const ckks_key* rlk, uint64_t* d_out, void* d_ws, size_t ws_bytes, void* stream);
+
+/* Optional per-kernel timing, for benchmarks (not part of the paper's method; callers that measure).
+ * Between ckks_prof_begin and ckks_prof_end every launch of a kernel class whose bit is set in
+ * kernel_mask is bracketed by a HIP event pair on the stream it is launched on (at most
+ * max_launches pairs; later launches are counted as dropped).  ckks_prof_begin creates the events
+ * (not a hot call); ckks_prof_end waits for them and writes, per kernel class (arrays of
+ * ckks_prof_kernel_count() entries, any of them may be NULL): total milliseconds, launch count, the
+ * algorithmic HBM bytes of those launches (every operand read once, every result written once) and
+ * their modular multiplications (butterflies / multiply-adds); then it frees the events.
+ * One profiling session at a time per context; not thread-safe. */
+uint32_t ckks_prof_kernel_count(void);
+const char* ckks_prof_kernel_name(uint32_t id);
+int ckks_prof_begin(ckks_ctx* ctx, uint32_t kernel_mask, uint32_t max_launches);
+int ckks_prof_end(ckks_ctx* ctx, double* h_ms, uint64_t* h_launches, double* h_bytes, double* h_ops, uint64_t* h_dropped);
 
 #ifdef __cplusplus
 }

@@ -17,14 +17,20 @@
 //     out[k] = a(psi^(2*brv(k)+1)); the inverse is its exact inverse including 1/N;
 //   * digit j of a hybrid key switch covers limbs [j*alpha, (j+1)*alpha) intersected with the live
 //     limbs, alpha = ceil(num_q / dnum);
-//   * the scaled residue y_i = [c_i * (Q_j/q_i)^-1] mod q_i is taken in [0, q_i) and the basis
-//     extension is the plain (uncorrected) sum  sum_i y_i * [Q_j/q_i]_t  mod t, so the extended
-//     digit equals c + u*Q_j with an integer 0 <= u < |digit|;
-//   * ModDown uses the same uncorrected extension of the P-part and no rounding term;
+//   * the scaled residue y_i = [c_i * (Q_j/q_i)^-1] mod q_i is taken as the CENTRED representative
+//     in [-(q_i-1)/2, (q_i-1)/2] and the basis extension is the plain sum
+//     sum_i y_i * [Q_j/q_i]_t  mod t  (no floating-point correction), so the extended digit equals
+//     c + u*Q_j with a small integer |u| <= |digit|/2 of mean zero;
+//   * ModDown extends the P-part the same way (centred, uncorrected), which makes the division by
+//     P a rounding to nearest with an extra error below k/2 of mean zero.  (Unsigned
+//     representatives would bias every coefficient by about -k/2; times the secret that is a
+//     low-frequency error of ~1e-4 in the slots at N = 2^16 and scale 2^40.)
 //   * rescale takes the centred remainder of the dropped limb (round to nearest);
-//   * a rotation can be computed in two orders that give different integers (same plaintext up to
-//     noise): "unhoisted" applies the automorphism to the ciphertext first and key-switches the
-//     permuted c1; "hoisted" extends c1 once and permutes the extended digits.  Both are here.
+//   * a rotation can be computed in two orders: "unhoisted" applies the automorphism to the
+//     ciphertext first and key-switches the permuted c1; "hoisted" extends c1 once and permutes the
+//     extended digits.  Both are here.  Because the automorphism only permutes and negates
+//     coefficients and centring commutes with negation, the two orders give the same residues
+//     (with unsigned representatives they would differ by multiples of Q_j).
 //   * sampling (oracle only): SplitMix64-seeded xoshiro256**, ternary secret uniform on {-1,0,1},
 //     error = round(3.2 * Box-Muller normal) truncated to |e| <= 19, uniform residues by rejection.
 //
@@ -252,7 +258,12 @@ void orc_modup(void* h, int level, const u64* cin, u64* digits) {
             }
             for (int x = 0; x < N; x++) {
                 u64 acc = 0;
-                for (int a = 0; a < nd; a++) acc = addmod(acc, mulmod(y[(size_t)a * N + x] % qt, qhat_t[a], qt), qt);
+                for (int a = 0; a < nd; a++) {
+                    u64 qa = c->mod[lo + a], ya = y[(size_t)a * N + x];
+                    u64 yt = ya % qt;                                  // centred y_a reduced modulo t
+                    if (ya > qa / 2) yt = submod(yt, qa % qt, qt);     // (y_a - q_a) mod t
+                    acc = addmod(acc, mulmod(yt, qhat_t[a], qt), qt);
+                }
                 out[x] = acc;
             }
             orc_ntt_fwd(h, t, out);
@@ -280,7 +291,7 @@ void orc_key_inner(void* h, int level, const u64* digits, const u64* key, u64* v
         }
 }
 
-// ModDown: v[level+1+k][N] (NTT form) -> u[level+1][N] (NTT form), u = (v - ext(v mod P)) / P.
+// ModDown: v[level+1+k][N] (NTT form) -> u[level+1][N] (NTT form), u = (v - ext([v]_P centred)) / P.
 void orc_moddown(void* h, int level, const u64* v, u64* u) {
     Ctx* c = (Ctx*)h;
     int N = c->N, k = c->num_p;
@@ -312,7 +323,12 @@ void orc_moddown(void* h, int level, const u64* v, u64* u) {
         std::vector<u64> w(N);
         for (int x = 0; x < N; x++) {
             u64 acc = 0;
-            for (int a = 0; a < k; a++) acc = addmod(acc, mulmod(z[(size_t)a * N + x] % qi, phat_i[a], qi), qi);
+            for (int a = 0; a < k; a++) {
+                u64 pa = c->mod[c->num_q + a], za = z[(size_t)a * N + x];
+                u64 zi = za % qi;                                  // centred z_a reduced modulo q_i
+                if (za > pa / 2) zi = submod(zi, pa % qi, qi);     // (z_a - p_a) mod q_i
+                acc = addmod(acc, mulmod(zi, phat_i[a], qi), qi);
+            }
             w[x] = acc;
         }
         orc_ntt_fwd(h, i, w.data());

@@ -37,6 +37,7 @@ EXPORTS = (
     "ckks_ntt_fwd", "ckks_ntt_inv", "ckks_key_load", "ckks_key_free", "ckks_galois_element",
     "ckks_keyswitch", "ckks_rotate_hoisted", "ckks_ptct_mac", "ckks_rescale", "ckks_ctct_mul_relin",
     "he_conv_workspace_bytes", "he_conv_batched", "he_poly_act_deg7",
+    "ckks_prof_kernel_count", "ckks_prof_kernel_name", "ckks_prof_begin", "ckks_prof_end",
 )
 
 _expect_device = "cuda"  # tensors handed to the library must live here
@@ -86,6 +87,11 @@ def _bind(path: str):
     lib.he_conv_workspace_bytes.restype = sz
     lib.he_conv_batched.argtypes = [vp, C.POINTER(_ConvDesc), C.POINTER(vp), C.POINTER(vp), vp, vp, C.POINTER(vp), vp, sz, vp]
     lib.he_poly_act_deg7.argtypes = [vp, vp, u32, C.POINTER(C.c_int64), vp, vp, vp, sz, vp]
+    lib.ckks_prof_kernel_count.restype = u32
+    lib.ckks_prof_kernel_name.argtypes = [u32]
+    lib.ckks_prof_kernel_name.restype = C.c_char_p
+    lib.ckks_prof_begin.argtypes = [vp, u32, u32]
+    lib.ckks_prof_end.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_uint64), C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_uint64)]
     return lib
 
 
@@ -174,7 +180,7 @@ class Context:
 
     def workspace(self, nbytes: int) -> torch.Tensor:
         """A cached scratch tensor of at least nbytes (grown on demand, reused across calls)."""
-        if self._ws is None or self._ws.numel() < nbytes:
+        if self._ws is None or self._ws.numel() * self._ws.element_size() < nbytes:
             self._ws = torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=_expect_device)
         return self._ws
 
@@ -223,7 +229,7 @@ def ckks_keyswitch(ctx: Context, c: torch.Tensor, level: int, key: Key, out: Opt
     if out is None:
         out = empty(2, level + 1, ctx.N)
     ws = _ws(ctx, ws, ckks_workspace_bytes(ctx, CKKS_OP_KEYSWITCH, level))
-    ctx._check(_lib.ckks_keyswitch(ctx.handle, _ptr(c), level, key.handle if key else None, _ptr(out), _ptr(ws), ws.numel(), _stream(stream)))
+    ctx._check(_lib.ckks_keyswitch(ctx.handle, _ptr(c), level, key.handle if key else None, _ptr(out), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)))
     return out
 
 
@@ -242,7 +248,7 @@ def ckks_rotate_hoisted(ctx: Context, ct: torch.Tensor, level: int, offsets: Seq
     offs = (C.c_int32 * n)(*[int(r) for r in offsets])
     ks = _ptr_array([k.handle.value if k is not None else None for k in keys])
     os_ = _ptr_array([_ptr(o) for o in outs])
-    ctx._check(_lib.ckks_rotate_hoisted(ctx.handle, _ptr(ct), level, offs, n, ks, os_, int(bool(hoisted)), _ptr(ws), ws.numel(), _stream(stream)))
+    ctx._check(_lib.ckks_rotate_hoisted(ctx.handle, _ptr(ct), level, offs, n, ks, os_, int(bool(hoisted)), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)))
     return outs
 
 
@@ -273,7 +279,7 @@ def ckks_rescale(ctx: Context, ct: torch.Tensor, level: int, out: Optional[torch
     if out is None:
         out = empty(2, max(level, 1), ctx.N)
     ws = _ws(ctx, ws, ckks_workspace_bytes(ctx, CKKS_OP_RESCALE, level))
-    ctx._check(_lib.ckks_rescale(ctx.handle, _ptr(ct), level, _ptr(out), _ptr(ws), ws.numel(), _stream(stream)))
+    ctx._check(_lib.ckks_rescale(ctx.handle, _ptr(ct), level, _ptr(out), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)))
     return out
 
 
@@ -284,7 +290,7 @@ def ckks_ctct_mul_relin(ctx: Context, a: torch.Tensor, b: torch.Tensor, level: i
     if out is None:
         out = empty(2, level + 1, ctx.N)
     ws = _ws(ctx, ws, ckks_workspace_bytes(ctx, CKKS_OP_CTCT_MUL_RELIN, level))
-    ctx._check(_lib.ckks_ctct_mul_relin(ctx.handle, _ptr(a), _ptr(b), level, rlk.handle if rlk else None, _ptr(out), _ptr(ws), ws.numel(), _stream(stream)))
+    ctx._check(_lib.ckks_ctct_mul_relin(ctx.handle, _ptr(a), _ptr(b), level, rlk.handle if rlk else None, _ptr(out), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)))
     return out
 
 
@@ -317,7 +323,7 @@ def he_conv_batched(ctx: Context, height: int, width: int, batch: int, level: in
     ia = _ptr_array([_ptr(t) for t in ins])
     ka = _ptr_array([k.handle.value if k is not None else None for k in rot_keys])
     oa = _ptr_array([_ptr(o) for o in outs])
-    ctx._check(_lib.he_conv_batched(ctx.handle, C.byref(d), ia, ka, _ptr(tap_masks), _ptr(w_res), oa, _ptr(ws), ws.numel(), _stream(stream)))
+    ctx._check(_lib.he_conv_batched(ctx.handle, C.byref(d), ia, ka, _ptr(tap_masks), _ptr(w_res), oa, _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)))
     return outs
 
 
@@ -329,5 +335,33 @@ def he_poly_act_deg7(ctx: Context, x: torch.Tensor, level: int, k: Sequence[int]
         out = empty(2, max(level - 3, 1), ctx.N)
     ws = _ws(ctx, ws, ckks_workspace_bytes(ctx, CKKS_OP_POLY_ACT, level))
     ka = (C.c_int64 * 4)(*[int(v) for v in k])
-    ctx._check(_lib.he_poly_act_deg7(ctx.handle, _ptr(x), level, ka, rlk.handle if rlk else None, _ptr(out), _ptr(ws), ws.numel(), _stream(stream)))
+    ctx._check(_lib.he_poly_act_deg7(ctx.handle, _ptr(x), level, ka, rlk.handle if rlk else None, _ptr(out), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)))
+    return out
+
+
+def ckks_prof_kernel_names() -> List[str]:
+    return [_lib.ckks_prof_kernel_name(i).decode() for i in range(_lib.ckks_prof_kernel_count())]
+
+
+def ckks_prof_begin(ctx: Context, kernels: Optional[Sequence[str]] = None, max_launches: int = 65536) -> None:
+    """Start bracketing launches of the named kernel classes (default: all) with HIP events."""
+    names = ckks_prof_kernel_names()
+    mask = 0
+    for k in (names if kernels is None else kernels):
+        mask |= 1 << names.index(k)
+    ctx._check(_lib.ckks_prof_begin(ctx.handle, mask, max_launches))
+
+
+def ckks_prof_end(ctx: Context) -> dict:
+    """{kernel: dict(ms, launches, bytes, ops)} for the classes that ran, plus the key "dropped"."""
+    n = _lib.ckks_prof_kernel_count()
+    ms = (C.c_double * n)()
+    cnt = (C.c_uint64 * n)()
+    nbytes = (C.c_double * n)()
+    ops = (C.c_double * n)()
+    dropped = C.c_uint64()
+    ctx._check(_lib.ckks_prof_end(ctx.handle, ms, cnt, nbytes, ops, C.byref(dropped)))
+    out = {name: dict(ms=ms[i], launches=int(cnt[i]), bytes=nbytes[i], ops=ops[i])
+           for i, name in enumerate(ckks_prof_kernel_names()) if cnt[i]}
+    out["dropped"] = int(dropped.value)
     return out

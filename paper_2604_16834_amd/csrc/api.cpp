@@ -400,6 +400,66 @@ int he_conv_batched(const ckks_ctx* c, const he_conv_desc* d, const uint64_t* co
     return CKKS_OK;
 }
 
+// ---- optional per-kernel timing -------------------------------------------------------------------
+static const char* const kKernelNames[K_COUNT] = {
+    "ntt_fwd_hi", "ntt_fwd_lo", "ntt_inv_lo", "ntt_inv_hi", "modup_conv", "key_inner", "moddown_conv", "moddown_final",
+    "automorph", "copy", "ptct_mac", "rescale_conv", "rescale_final", "tensor", "mask_mul", "weighted_sum", "lincomb2"};
+
+uint32_t ckks_prof_kernel_count(void) { return K_COUNT; }
+const char* ckks_prof_kernel_name(uint32_t id) { return id < K_COUNT ? kKernelNames[id] : ""; }
+
+int ckks_prof_begin(ckks_ctx* c, uint32_t kernel_mask, uint32_t max_launches) {
+    if (!c) return CKKS_ERR_INVALID_ARG;
+    if (c->prof) return set_err(c, CKKS_ERR_INVALID_ARG, "profiling already on");
+    if (max_launches == 0) return set_err(c, CKKS_ERR_INVALID_ARG, "max_launches must be positive");
+    ProfState* p = new (std::nothrow) ProfState;
+    if (!p) return set_err(c, CKKS_ERR_INVALID_ARG, "out of host memory");
+    p->mask = kernel_mask;
+    p->events.resize(2 * (size_t)max_launches);
+    p->kernel_of_pair.resize(max_launches);
+    for (size_t i = 0; i < p->events.size(); i++) {
+        hipError_t e = hipEventCreate(&p->events[i]);
+        if (e != hipSuccess) {
+            for (size_t j = 0; j < i; j++) (void)hipEventDestroy(p->events[j]);
+            delete p;
+            c->err = std::string("hipEventCreate: ") + hipGetErrorString(e);
+            return CKKS_ERR_HIP;
+        }
+    }
+    c->prof = p;
+    return CKKS_OK;
+}
+
+int ckks_prof_end(ckks_ctx* c, double* h_ms, uint64_t* h_launches, double* h_bytes, double* h_ops, uint64_t* h_dropped) {
+    if (!c) return CKKS_ERR_INVALID_ARG;
+    ProfState* p = c->prof;
+    if (!p) return set_err(c, CKKS_ERR_INVALID_ARG, "profiling is not on");
+    c->prof = nullptr;
+    int rc = CKKS_OK;
+    for (u32 k = 0; k < K_COUNT; k++) {
+        if (h_ms) h_ms[k] = 0.0;
+        if (h_launches) h_launches[k] = 0;
+        if (h_bytes) h_bytes[k] = p->bytes[k];
+        if (h_ops) h_ops[k] = p->ops[k];
+    }
+    for (size_t i = 0; i < p->used_pairs && rc == CKKS_OK; i++) {
+        hipError_t e = hipEventSynchronize(p->events[2 * i + 1]);
+        float ms = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, p->events[2 * i], p->events[2 * i + 1]);
+        if (e != hipSuccess) {
+            c->err = std::string("profiling events: ") + hipGetErrorString(e);
+            rc = CKKS_ERR_HIP;
+            break;
+        }
+        if (h_ms) h_ms[p->kernel_of_pair[i]] += ms;
+        if (h_launches) h_launches[p->kernel_of_pair[i]]++;
+    }
+    if (h_dropped) *h_dropped = p->dropped;
+    for (hipEvent_t ev : p->events) (void)hipEventDestroy(ev);
+    delete p;
+    return rc;
+}
+
 int he_poly_act_deg7(const ckks_ctx* c, const uint64_t* d_x, uint32_t level, const int64_t* h_k, const ckks_key* rlk,
                      uint64_t* d_out, void* d_ws, size_t ws_bytes, void* stream) {
     if (!c) return CKKS_ERR_INVALID_ARG;

@@ -97,7 +97,7 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
     }
     // products of two residues are below 2^(2*bmax); a Barrett input must stay below 2^(62+bmin)
     const int lazy_log = 62 + (int)bmin - 2 * (int)bmax;
-    if (lazy_log < 4) return fail(CKKS_ERR_UNSUPPORTED_PARAMS, "moduli sizes too uneven for 128-bit lazy accumulation");
+    if (lazy_log < 5) return fail(CKKS_ERR_UNSUPPORTED_PARAMS, "moduli sizes too uneven for 128-bit lazy accumulation");
 
     ckks_ctx* c = new (std::nothrow) ckks_ctx;
     if (!c) return fail(CKKS_ERR_INVALID_ARG, "out of host memory");
@@ -156,13 +156,19 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
                         tab[2 * alpha + (size_t)a * M + e] = v;
                     }
                 }
+                for (u32 e = 0; e < E; e++) {  // -Q_j mod t: one per centred digit limb that is negative
+                    const u64 qt = c->mod[c->ext_modulus(level, e)];
+                    u64 Q = 1;
+                    for (u32 b = lo; b < hi; b++) Q = h_mulmod(Q, c->mod[b] % qt, qt);
+                    tab[(size_t)alpha * (2 + M) + e] = (qt - Q) % qt;
+                }
             }
     }
     // ModDown table
     std::vector<u64> moddown;
     if (c->dnum) {
         const u32 k = c->num_p, nq = c->num_q;
-        moddown.assign(2 * k + (size_t)k * nq + 2 * nq, 0);
+        moddown.assign(2 * k + (size_t)k * nq + 3 * nq, 0);
         for (u32 a = 0; a < k; a++) {
             const u64 pa = c->mod[nq + a];
             u64 phat = 1;
@@ -184,6 +190,7 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
             const u64 pinv = h_invmod(P, qi);
             moddown[2 * k + (size_t)k * nq + i] = pinv;
             moddown[2 * k + (size_t)k * nq + nq + i] = h_shoup(pinv, qi);
+            moddown[2 * k + (size_t)k * nq + 2 * nq + i] = (qi - P) % qi;  // -P mod q_i
         }
     }
     // rescale table [l][i] = (q_l^-1 mod q_i, Shoup companion, q_l mod q_i)

@@ -21,6 +21,21 @@ struct PolyList {
     unsigned char mod[CKKS_MAX_MODULI];
 };
 
+// kernel classes, for the optional per-kernel timing (ckks_prof_begin / ckks_prof_end)
+enum KernelId {
+    K_NTT_FWD_HI = 0, K_NTT_FWD_LO, K_NTT_INV_LO, K_NTT_INV_HI, K_MODUP_CONV, K_KEY_INNER, K_MODDOWN_CONV, K_MODDOWN_FINAL,
+    K_AUTOMORPH, K_COPY, K_PTCT_MAC, K_RESCALE_CONV, K_RESCALE_FINAL, K_TENSOR, K_MASK_MUL, K_WEIGHTED_SUM, K_LINCOMB2, K_COUNT
+};
+
+struct ProfState {
+    std::vector<hipEvent_t> events;  // pairs (start, stop)
+    std::vector<int> kernel_of_pair;
+    size_t used_pairs = 0, dropped = 0;
+    u32 mask = 0;
+    double bytes[K_COUNT] = {0};  // algorithmic HBM bytes of the recorded launches
+    double ops[K_COUNT] = {0};    // modular multiplications (butterflies, multiply-adds) of the recorded launches
+};
+
 struct ckks_key {
     const u64* d_key;
     u32 galois_elt;
@@ -40,21 +55,43 @@ struct ckks_ctx {
     u64* d_itw = nullptr;             // [M][N]  psi^-bitrev(i)
     u64* d_itw_sh = nullptr;
     u64* d_modup = nullptr;           // per level, per digit: see modup_digit_stride()
-    u64* d_moddown = nullptr;         // phat_inv[k], phat_inv_sh[k], phat_q[k][num_q], pinv[num_q], pinv_sh[num_q]
+    u64* d_moddown = nullptr;         // phat_inv[k], phat_inv_sh[k], phat_q[k][num_q], pinv[num_q], pinv_sh[num_q], negp[num_q]
     u64* d_rescale = nullptr;         // [num_q][num_q][3]: (q_l^-1 mod q_i, its Shoup companion, q_l mod q_i)
 
     mutable std::string err;
+    mutable ProfState* prof = nullptr;  // non-null between ckks_prof_begin and ckks_prof_end
 
     u32 ext_limbs(u32 level) const { return level + 1 + num_p; }
     u32 live_digits(u32 level) const { return (level + alpha) / alpha; }
     u32 digit_lo(u32 j) const { return j * alpha; }
     u32 digit_hi(u32 j, u32 level) const { u32 h = (j + 1) * alpha; return h < level + 1 ? h : level + 1; }
     u32 ext_modulus(u32 level, u32 e) const { return e <= level ? e : num_q + (e - level - 1); }
-    // ModUp table of one digit: inv[alpha], inv_sh[alpha], conv[alpha][M] (conv indexed by the
-    // position e in the extended basis of that level)
-    size_t modup_digit_stride() const { return (size_t)alpha * (2 + M); }
+    // ModUp table of one digit: inv[alpha], inv_sh[alpha], conv[alpha][M], negq[M] (conv and negq
+    // indexed by the position e in the extended basis of that level; negq = -Q_j mod t)
+    size_t modup_digit_stride() const { return (size_t)alpha * (2 + M) + M; }
     size_t modup_level_stride() const { return modup_digit_stride() * dnum; }
     const u64* modup_table(u32 level, u32 j) const { return d_modup + level * modup_level_stride() + j * modup_digit_stride(); }
+};
+
+// Records a (start, stop) event pair around one kernel launch while profiling is on.
+struct ProfScope {
+    const ckks_ctx* c;
+    hipStream_t st;
+    long pair;
+    // bytes: what the launch must read and write at least once; ops: its modular multiplications
+    ProfScope(const ckks_ctx* ctx, int kernel, hipStream_t s, double bytes, double ops) : c(ctx), st(s), pair(-1) {
+        ProfState* p = c->prof;
+        if (!p || !((p->mask >> kernel) & 1u)) return;
+        if (2 * (p->used_pairs + 1) > p->events.size()) { p->dropped++; return; }
+        pair = (long)p->used_pairs++;
+        p->kernel_of_pair[pair] = kernel;
+        p->bytes[kernel] += bytes;
+        p->ops[kernel] += ops;
+        (void)hipEventRecord(p->events[2 * pair], st);
+    }
+    ~ProfScope() {
+        if (pair >= 0) (void)hipEventRecord(c->prof->events[2 * pair + 1], st);
+    }
 };
 
 // ---- kernel launchers (each enqueues on `st` and returns the launch status) -------------------

@@ -3,11 +3,14 @@
 // Parameters": key switching with digits).
 //
 //   ModUp      digit j's limbs (coefficient form) -> all live q-limbs and the special primes:
-//              y_a = [c_a * (Q_j/q_a)^-1] mod q_a  in [0, q_a),
-//              d_j[t] = sum_a y_a * [Q_j/q_a]_t  mod t          (plain sum, no correction term)
+//              y_a = [c_a * (Q_j/q_a)^-1] mod q_a  taken centred in [-(q_a-1)/2, (q_a-1)/2],
+//              d_j[t] = sum_a y_a * [Q_j/q_a]_t  mod t          (plain sum, no correction term).
+//              Computed on the unsigned residues plus  (#negative y_a) * (-Q_j mod t), which is
+//              the same integer modulo t because q_a * (Q_j/q_a) = Q_j.
 //   inner      v_comp[t] = sum_j sigma_g(d_j)[t] * key[j][comp][t]   (sigma_g = gather, g = 1: none)
-//   ModDown    z_a = [v_{p_a} * (P/p_a)^-1] mod p_a,  w[i] = sum_a z_a * [P/p_a]_{q_i}  (coefficient
-//              form), then in NTT form u[i] = (v[q_i] - w[i]) * P^-1  (+ an optional addend)
+//   ModDown    z_a = [v_{p_a} * (P/p_a)^-1] mod p_a centred,  w[i] = sum_a z_a * [P/p_a]_{q_i}
+//              (coefficient form, same negative-count trick with -P mod q_i), then in NTT form
+//              u[i] = (v[q_i] - w[i]) * P^-1  (+ an optional addend)
 // Sums of products are accumulated unreduced in 128 bits and reduced once.
 #include "ctx.h"
 
@@ -33,9 +36,15 @@ __global__ __launch_bounds__(KS_THREADS) void modup_conv_kernel(const u64* __res
     const u32 x = blockIdx.x * KS_THREADS + threadIdx.x;
     if (x >= N) return;
     u64 yv[KS_MAX_DIGIT];
+    u64 n_neg = 0;
 #pragma unroll
     for (u32 a = 0; a < KS_MAX_DIGIT; a++)
-        if (a < nd) yv[a] = mul_shoup(y[(size_t)a * N + x], tab[a], tab[alpha + a], mc[lo + a].q);
+        if (a < nd) {
+            const u64 qa = mc[lo + a].q;
+            yv[a] = mul_shoup(y[(size_t)a * N + x], tab[a], tab[alpha + a], qa);
+            n_neg += yv[a] > (qa >> 1) ? 1 : 0;
+        }
+    const u64* negq = tab + (size_t)alpha * (2 + M);
     const u32 e0 = blockIdx.y * MODUP_LIMBS_PER_BLOCK;
     for (u32 e = e0; e < e0 + MODUP_LIMBS_PER_BLOCK && e < E; e++) {
         const u32 t = e <= level ? e : num_q + (e - level - 1);
@@ -47,6 +56,7 @@ __global__ __launch_bounds__(KS_THREADS) void modup_conv_kernel(const u64* __res
 #pragma unroll
         for (u32 a = 0; a < KS_MAX_DIGIT; a++)
             if (a < nd) acc_wide(acc, yv[a], tab[2 * alpha + (size_t)a * M + e]);
+        acc_wide(acc, n_neg, negq[e]);
         digit[(size_t)e * N + x] = barrett_reduce(acc, mc[t]);
     }
 }
@@ -54,8 +64,8 @@ __global__ __launch_bounds__(KS_THREADS) void modup_conv_kernel(const u64* __res
 hipError_t launch_modup_conv(const ckks_ctx* c, u32 level, u32 j, const u64* y, const u64* c_in, u64* digit, hipStream_t st) {
     const u32 E = c->ext_limbs(level), lo = c->digit_lo(j), nd = c->digit_hi(j, level) - lo;
     dim3 grid((c->N + KS_THREADS - 1) / KS_THREADS, (E + MODUP_LIMBS_PER_BLOCK - 1) / MODUP_LIMBS_PER_BLOCK);
-    hipLaunchKernelGGL(modup_conv_kernel, grid, dim3(KS_THREADS), 0, st, y, c_in, digit, c->modup_table(level, j), c->d_mc,
-                       c->N, level, c->num_q, lo, nd, c->alpha, c->M, E);
+    { ProfScope ps__(c, K_MODUP_CONV, st, 8.0 * c->N * (2.0 * nd + E), (double)c->N * nd * (1.0 + E - nd)); hipLaunchKernelGGL(modup_conv_kernel, grid, dim3(KS_THREADS), 0, st, y, c_in, digit, c->modup_table(level, j), c->d_mc,
+                       c->N, level, c->num_q, lo, nd, c->alpha, c->M, E); }
     return hipGetLastError();
 }
 
@@ -88,8 +98,8 @@ __global__ __launch_bounds__(KS_THREADS) void key_inner_kernel(const u64* __rest
 hipError_t launch_key_inner(const ckks_ctx* c, u32 level, const u64* digits, const u64* key, u32 g, u64* v, hipStream_t st) {
     const u32 E = c->ext_limbs(level);
     dim3 grid((c->N + KS_THREADS - 1) / KS_THREADS, E);
-    hipLaunchKernelGGL(key_inner_kernel, grid, dim3(KS_THREADS), 0, st, digits, key, v, c->d_mc, c->log_n, level, c->num_q,
-                       c->M, E, c->live_digits(level), g);
+    { ProfScope ps__(c, K_KEY_INNER, st, 8.0 * c->N * E * (3.0 * c->live_digits(level) + 2.0), 2.0 * c->N * E * c->live_digits(level)); hipLaunchKernelGGL(key_inner_kernel, grid, dim3(KS_THREADS), 0, st, digits, key, v, c->d_mc, c->log_n, level, c->num_q,
+                       c->M, E, c->live_digits(level), g); }
     return hipGetLastError();
 }
 
@@ -103,24 +113,31 @@ __global__ __launch_bounds__(KS_THREADS) void moddown_conv_kernel(const u64* __r
     if (x >= N) return;
     const u32 comp = blockIdx.z;
     u64 z[KS_MAX_DIGIT];
+    u64 n_neg = 0;
 #pragma unroll
     for (u32 a = 0; a < KS_MAX_DIGIT; a++)
-        if (a < k) z[a] = mul_shoup(v[((size_t)comp * E + level + 1 + a) * N + x], tab[a], tab[k + a], mc[num_q + a].q);
+        if (a < k) {
+            const u64 pa = mc[num_q + a].q;
+            z[a] = mul_shoup(v[((size_t)comp * E + level + 1 + a) * N + x], tab[a], tab[k + a], pa);
+            n_neg += z[a] > (pa >> 1) ? 1 : 0;
+        }
     const u64* phat_q = tab + 2 * k;  // [k][num_q]
+    const u64* negp = tab + 2 * k + (size_t)k * num_q + 2 * num_q;
     const u32 i0 = blockIdx.y * MODDOWN_LIMBS_PER_BLOCK;
     for (u32 i = i0; i < i0 + MODDOWN_LIMBS_PER_BLOCK && i <= level; i++) {
         U128 acc = {0, 0};
 #pragma unroll
         for (u32 a = 0; a < KS_MAX_DIGIT; a++)
             if (a < k) acc_wide(acc, z[a], phat_q[(size_t)a * num_q + i]);
+        acc_wide(acc, n_neg, negp[i]);
         w[((size_t)comp * (level + 1) + i) * N + x] = barrett_reduce(acc, mc[i]);
     }
 }
 
 hipError_t launch_moddown_conv(const ckks_ctx* c, u32 level, const u64* v, u64* w, hipStream_t st) {
     dim3 grid((c->N + KS_THREADS - 1) / KS_THREADS, (level + 1 + MODDOWN_LIMBS_PER_BLOCK - 1) / MODDOWN_LIMBS_PER_BLOCK, 2);
-    hipLaunchKernelGGL(moddown_conv_kernel, grid, dim3(KS_THREADS), 0, st, v, w, c->d_moddown, c->d_mc, c->N, level,
-                       c->num_q, c->num_p, c->ext_limbs(level));
+    { ProfScope ps__(c, K_MODDOWN_CONV, st, 16.0 * c->N * (c->num_p + level + 1.0), 2.0 * c->N * c->num_p * (level + 2.0)); hipLaunchKernelGGL(moddown_conv_kernel, grid, dim3(KS_THREADS), 0, st, v, w, c->d_moddown, c->d_mc, c->N, level,
+                       c->num_q, c->num_p, c->ext_limbs(level)); }
     return hipGetLastError();
 }
 
@@ -151,7 +168,7 @@ __global__ __launch_bounds__(KS_THREADS) void moddown_final_kernel(const u64* __
 hipError_t launch_moddown_final(const ckks_ctx* c, u32 level, const u64* v, const u64* w, const u64* add0, const u64* add1,
                                 u32 g, u64* out, hipStream_t st) {
     dim3 grid((c->N + KS_THREADS - 1) / KS_THREADS, level + 1, 2);
-    hipLaunchKernelGGL(moddown_final_kernel, grid, dim3(KS_THREADS), 0, st, v, w, add0, add1, out, c->d_moddown, c->d_mc,
-                       c->log_n, level, c->num_q, c->num_p, c->ext_limbs(level), g);
+    { ProfScope ps__(c, K_MODDOWN_FINAL, st, 8.0 * c->N * (level + 1.0) * (6.0 + (add0 ? 1.0 : 0.0) + (add1 ? 1.0 : 0.0)), 2.0 * c->N * (level + 1.0)); hipLaunchKernelGGL(moddown_final_kernel, grid, dim3(KS_THREADS), 0, st, v, w, add0, add1, out, c->d_moddown, c->d_mc,
+                       c->log_n, level, c->num_q, c->num_p, c->ext_limbs(level), g); }
     return hipGetLastError();
 }

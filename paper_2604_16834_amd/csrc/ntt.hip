@@ -221,23 +221,23 @@ hipError_t launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, size_t sr
         A.tw_sh = c->d_tw_sh;
         A.last = 1;
         if (c->log_hi > 0) {
-            hipLaunchKernelGGL(ntt_fwd_hi_kernel, grid_hi, block, 0, st, A, pl);
+            { ProfScope ps__(c, K_NTT_FWD_HI, st, 16.0 * polys * c->N, 0.5 * polys * c->N * c->log_hi); hipLaunchKernelGGL(ntt_fwd_hi_kernel, grid_hi, block, 0, st, A, pl); }
             // the lo pass continues in place on dst
             NttArgs B = A;
             B.src = dst;
             B.src_bstride = dst_bstride;
             PolyList pd = pl;
             for (u32 i = 0; i < pl.n; i++) pd.spos[i] = pl.dpos[i];
-            hipLaunchKernelGGL(ntt_fwd_lo_kernel, grid_lo, block, 0, st, B, pd);
+            { ProfScope ps__(c, K_NTT_FWD_LO, st, 16.0 * polys * c->N, 0.5 * polys * c->N * c->log_lo); hipLaunchKernelGGL(ntt_fwd_lo_kernel, grid_lo, block, 0, st, B, pd); }
         } else {
-            hipLaunchKernelGGL(ntt_fwd_lo_kernel, grid_lo, block, 0, st, A, pl);
+            { ProfScope ps__(c, K_NTT_FWD_LO, st, 16.0 * polys * c->N, 0.5 * polys * c->N * c->log_lo); hipLaunchKernelGGL(ntt_fwd_lo_kernel, grid_lo, block, 0, st, A, pl); }
         }
     } else {
         A.tw = c->d_itw;
         A.tw_sh = c->d_itw_sh;
         A.last = c->log_hi == 0;
-        hipLaunchKernelGGL(ntt_inv_lo_kernel, grid_lo, block, 0, st, A, pl);
-        if (c->log_hi > 0) hipLaunchKernelGGL(ntt_inv_hi_kernel, grid_hi, block, 0, st, A, pl);
+        { ProfScope ps__(c, K_NTT_INV_LO, st, 16.0 * polys * c->N, 0.5 * polys * c->N * c->log_lo); hipLaunchKernelGGL(ntt_inv_lo_kernel, grid_lo, block, 0, st, A, pl); }
+        if (c->log_hi > 0) { ProfScope ps__(c, K_NTT_INV_HI, st, 16.0 * polys * c->N, 0.5 * polys * c->N * c->log_hi); hipLaunchKernelGGL(ntt_inv_hi_kernel, grid_hi, block, 0, st, A, pl); }
     }
     return hipGetLastError();
 }

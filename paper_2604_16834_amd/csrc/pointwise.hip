@@ -24,7 +24,7 @@ __global__ __launch_bounds__(PW_THREADS) void automorph_kernel(const u64* __rest
 
 hipError_t launch_automorph(const ckks_ctx* c, u32 n_polys, const u64* in, u32 g, u64* out, hipStream_t st) {
     dim3 grid((c->N + PW_THREADS - 1) / PW_THREADS, n_polys);
-    hipLaunchKernelGGL(automorph_kernel, grid, dim3(PW_THREADS), 0, st, in, out, c->log_n, g);
+    { ProfScope ps__(c, K_AUTOMORPH, st, 16.0 * c->N * n_polys, 0.0); hipLaunchKernelGGL(automorph_kernel, grid, dim3(PW_THREADS), 0, st, in, out, c->log_n, g); }
     return hipGetLastError();
 }
 
@@ -73,7 +73,7 @@ hipError_t launch_ptct_mac(const ckks_ctx* c, u32 level, const u64* const* pts, 
             T.pt[k] = k < T.n ? pts[k0 + k] : nullptr;
             T.ct[k] = k < T.n ? cts[k0 + k] : nullptr;
         }
-        hipLaunchKernelGGL(ptct_mac_kernel, grid, dim3(PW_THREADS), 0, st, T, acc, c->d_mc, c->N, level, accumulate || k0 > 0);
+        { ProfScope ps__(c, K_PTCT_MAC, st, 8.0 * c->N * (level + 1.0) * (3.0 * T.n + 2.0 + ((accumulate || k0 > 0) ? 2.0 : 0.0)), 2.0 * c->N * (level + 1.0) * T.n); hipLaunchKernelGGL(ptct_mac_kernel, grid, dim3(PW_THREADS), 0, st, T, acc, c->d_mc, c->N, level, accumulate || k0 > 0); }
     }
     return hipGetLastError();
 }
@@ -96,7 +96,7 @@ __global__ __launch_bounds__(PW_THREADS) void rescale_conv_kernel(const u64* __r
 
 hipError_t launch_rescale_conv(const ckks_ctx* c, u32 level, const u64* r, u64* w, hipStream_t st) {
     dim3 grid((c->N + PW_THREADS - 1) / PW_THREADS, level, 2);
-    hipLaunchKernelGGL(rescale_conv_kernel, grid, dim3(PW_THREADS), 0, st, r, w, c->d_rescale, c->d_mc, c->N, level, c->num_q);
+    { ProfScope ps__(c, K_RESCALE_CONV, st, 16.0 * c->N * (1.0 + level), 0.0); hipLaunchKernelGGL(rescale_conv_kernel, grid, dim3(PW_THREADS), 0, st, r, w, c->d_rescale, c->d_mc, c->N, level, c->num_q); }
     return hipGetLastError();
 }
 
@@ -117,8 +117,8 @@ __global__ __launch_bounds__(PW_THREADS) void rescale_final_kernel(const u64* __
 
 hipError_t launch_rescale_final(const ckks_ctx* c, u32 level, const u64* ct, size_t ct_cstride, const u64* w, u64* out, hipStream_t st) {
     dim3 grid((c->N + PW_THREADS - 1) / PW_THREADS, level, 2);
-    hipLaunchKernelGGL(rescale_final_kernel, grid, dim3(PW_THREADS), 0, st, ct, ct_cstride, w, out, c->d_rescale, c->d_mc, c->N,
-                       level, c->num_q);
+    { ProfScope ps__(c, K_RESCALE_FINAL, st, 48.0 * c->N * level, 2.0 * c->N * level); hipLaunchKernelGGL(rescale_final_kernel, grid, dim3(PW_THREADS), 0, st, ct, ct_cstride, w, out, c->d_rescale, c->d_mc, c->N,
+                       level, c->num_q); }
     return hipGetLastError();
 }
 
@@ -144,7 +144,7 @@ __global__ __launch_bounds__(PW_THREADS) void tensor_kernel(const u64* __restric
 hipError_t launch_tensor(const ckks_ctx* c, u32 level, const u64* a, size_t a_cstride, const u64* b, size_t b_cstride, u64* d0,
                          u64* d1, u64* d2, hipStream_t st) {
     dim3 grid((c->N + PW_THREADS - 1) / PW_THREADS, level + 1);
-    hipLaunchKernelGGL(tensor_kernel, grid, dim3(PW_THREADS), 0, st, a, a_cstride, b, b_cstride, d0, d1, d2, c->d_mc, c->N);
+    { ProfScope ps__(c, K_TENSOR, st, 56.0 * c->N * (level + 1.0), 4.0 * c->N * (level + 1.0)); hipLaunchKernelGGL(tensor_kernel, grid, dim3(PW_THREADS), 0, st, a, a_cstride, b, b_cstride, d0, d1, d2, c->d_mc, c->N); }
     return hipGetLastError();
 }
 
@@ -161,7 +161,7 @@ __global__ __launch_bounds__(PW_THREADS) void mask_mul_kernel(const u64* __restr
 
 hipError_t launch_mask_mul(const ckks_ctx* c, u32 level, const u64* mask, const u64* ct, u64* out, hipStream_t st) {
     dim3 grid((c->N + PW_THREADS - 1) / PW_THREADS, level + 1, 2);
-    hipLaunchKernelGGL(mask_mul_kernel, grid, dim3(PW_THREADS), 0, st, mask, ct, out, c->d_mc, c->N, level);
+    { ProfScope ps__(c, K_MASK_MUL, st, 40.0 * c->N * (level + 1.0), 2.0 * c->N * (level + 1.0)); hipLaunchKernelGGL(mask_mul_kernel, grid, dim3(PW_THREADS), 0, st, mask, ct, out, c->d_mc, c->N, level); }
     return hipGetLastError();
 }
 
@@ -203,8 +203,8 @@ __global__ __launch_bounds__(PW_THREADS) void weighted_sum_kernel(const u64* __r
 hipError_t launch_weighted_sum(const ckks_ctx* c, u32 level, const u64* xs, u32 n_terms, const u64* w_res, u32 c_out, u64* acc,
                                hipStream_t st) {
     dim3 grid((c->N + PW_THREADS - 1) / PW_THREADS, 2 * (level + 1), (c_out + WS_OUT_TILE - 1) / WS_OUT_TILE);
-    hipLaunchKernelGGL(weighted_sum_kernel, grid, dim3(PW_THREADS), 0, st, xs, w_res, acc, c->d_mc, c->N, level, n_terms, c_out,
-                       c->lazy_terms);
+    { ProfScope ps__(c, K_WEIGHTED_SUM, st, 16.0 * c->N * (level + 1.0) * ((double)n_terms + c_out), 2.0 * c->N * (level + 1.0) * n_terms * c_out); hipLaunchKernelGGL(weighted_sum_kernel, grid, dim3(PW_THREADS), 0, st, xs, w_res, acc, c->d_mc, c->N, level, n_terms, c_out,
+                       c->lazy_terms); }
     return hipGetLastError();
 }
 
@@ -238,6 +238,6 @@ hipError_t launch_lincomb2(const ckks_ctx* c, u32 level, const u64* a, size_t a_
         K.kb[i] = i <= level ? kb[i] : 0;
     }
     dim3 grid((c->N + PW_THREADS - 1) / PW_THREADS, level + 1, 2);
-    hipLaunchKernelGGL(lincomb2_kernel, grid, dim3(PW_THREADS), 0, st, a, a_cstride, b, b_cstride, add, K, out, c->d_mc, c->N, level);
+    { ProfScope ps__(c, K_LINCOMB2, st, 16.0 * c->N * (level + 1.0) * (3.0 + (add ? 1.0 : 0.0)), 4.0 * c->N * (level + 1.0)); hipLaunchKernelGGL(lincomb2_kernel, grid, dim3(PW_THREADS), 0, st, a, a_cstride, b, b_cstride, add, K, out, c->d_mc, c->N, level); }
     return hipGetLastError();
 }

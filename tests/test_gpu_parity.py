@@ -1,0 +1,232 @@
+"""GPU parity: every exported operation, called through the C boundary, against the CPU oracle on
+the same seeded inputs -- bit-exact on every residue.  Sizes span several 2^11-point tiles, a
+ragged last digit, the lowest level and single-tile / sub-tile rings."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+if not torch.cuda.is_available():
+    pytest.skip("needs a GPU", allow_module_level=True)
+
+import paper_2604_16834_amd as hx  # noqa: E402
+from oracle import Oracle, conv2d_reference, activation_reference  # noqa: E402
+from workloads import CONFIGS, make_params, image_batch, conv_weights, conv_tap_offsets  # noqa: E402
+from gpu_common import rand_poly, rand_ct, w_residues  # noqa: E402
+
+
+def both(params):
+    return Oracle(params), hx.Context(params)
+
+
+# ------------------------------------------------------------------------------------------ NTT
+@pytest.mark.parametrize("log_n,bits", [(4, 20), (7, 30), (10, 50), (11, 50), (12, 50), (13, 50), (16, 50), (17, 50)])
+def test_ntt_matches_oracle(log_n, bits):
+    p = make_params(log_n, 3, 2, 1, bits=bits)
+    orc, ctx = both(p)
+    rng = np.random.default_rng(log_n)
+    idx = [4, 0, 2, 1]                       # any order of moduli, special primes included
+    batch = 3
+    polys = np.stack([rand_poly(rng, [p.moduli[t] for t in idx], orc.N) for _ in range(batch)])
+    polys[0, 0, :3] = (0, 1, p.moduli[idx[0]] - 1)
+    d = hx.from_host(polys)
+    hx.ckks_ntt_fwd(ctx, d, idx)
+    fwd = hx.to_host(d)
+    assert np.array_equal(fwd, orc.ntt_many(polys, idx))
+    hx.ckks_ntt_inv(ctx, d, idx)
+    assert np.array_equal(hx.to_host(d), polys)
+    d = hx.from_host(polys)
+    hx.ckks_ntt_inv(ctx, d, idx)
+    assert np.array_equal(hx.to_host(d), orc.ntt_many(polys, idx, inverse=True))
+
+
+def test_ntt_single_limb_single_poly():
+    p = make_params(12, 1, 0, 0)
+    orc, ctx = both(p)
+    a = rand_poly(np.random.default_rng(1), p.moduli, orc.N)
+    d = hx.from_host(a)
+    hx.ckks_ntt_fwd(ctx, d, [0], batch=1)
+    assert np.array_equal(hx.to_host(d)[0], orc.ntt_fwd(a[0], 0))
+
+
+# --------------------------------------------------------------------------------- key switching
+@pytest.fixture(scope="module")
+def ks_setup():
+    wl = CONFIGS["small_rotations"]          # N = 2^13, 7 limbs in digits of 3,3,1, 3 special primes
+    p = wl.params()
+    orc, ctx = both(p)
+    s, s_ntt = orc.gen_secret(11)
+    rlk = orc.gen_relin_key(s_ntt, 12)
+    return p, orc, ctx, s, s_ntt, rlk, hx.ckks_key_load(ctx, hx.from_host(rlk), 0)
+
+
+@pytest.mark.parametrize("level", [6, 5, 3, 2, 0])
+def test_keyswitch_matches_oracle(ks_setup, level):
+    p, orc, ctx, s, s_ntt, rlk, d_rlk = ks_setup
+    c = rand_poly(np.random.default_rng(20 + level), p.moduli[:level + 1], orc.N)
+    out = hx.ckks_keyswitch(ctx, hx.from_host(c), level, d_rlk)
+    assert np.array_equal(hx.to_host(out), orc.keyswitch(c, rlk, level))
+
+
+@pytest.mark.parametrize("level", [6, 4, 0])
+@pytest.mark.parametrize("hoisted", [True, False])
+def test_rotations_match_oracle(ks_setup, level, hoisted):
+    p, orc, ctx, s, s_ntt, rlk, d_rlk = ks_setup
+    rng = np.random.default_rng(30 + level)
+    z = rng.uniform(-1, 1, orc.n)
+    ct = orc.encrypt(z, 2.0 ** 40, level, s_ntt, 31)
+    offs = [1, -1, 64, 0, orc.n - 1, 1234, -orc.n]
+    keys = [orc.gen_rotation_key(s, s_ntt, r, 40 + i) if r % orc.n else None for i, r in enumerate(offs)]
+    dkeys = [hx.ckks_key_load(ctx, hx.from_host(k), hx.ckks_galois_element(ctx, r)) if k is not None else None
+             for k, r in zip(keys, offs)]
+    outs = hx.ckks_rotate_hoisted(ctx, hx.from_host(ct), level, offs, dkeys, hoisted)
+    want = orc.rotate_many(ct, level, offs, keys, hoisted)
+    for r, got, w in zip(offs, outs, want):
+        got = hx.to_host(got)
+        assert np.array_equal(got, w), f"offset {r}"
+        assert np.abs(orc.decrypt(got, level, s_ntt, 2.0 ** 40) - np.roll(z, -r)).max() < 1e-5
+
+
+def test_galois_element_matches_oracle(ks_setup):
+    p, orc, ctx, *_ = ks_setup
+    for r in (0, 1, -1, 5, orc.n - 1, orc.n, -orc.n - 3, 2 ** 20 + 7):
+        assert hx.ckks_galois_element(ctx, r) == orc.galois(r)
+
+
+# ------------------------------------------------------------------------------------ pointwise
+@pytest.mark.parametrize("n_terms", [1, 9, 16, 17, 40])
+def test_ptct_mac_matches_oracle(ks_setup, n_terms):
+    p, orc, ctx, *_ = ks_setup
+    level = 4
+    rng = np.random.default_rng(50 + n_terms)
+    pts = [rand_poly(rng, p.moduli[:level + 1], orc.N) for _ in range(n_terms)]
+    cts = [rand_ct(rng, p.moduli, level, orc.N) for _ in range(n_terms)]
+    dp, dc = [hx.from_host(x) for x in pts], [hx.from_host(x) for x in cts]
+    acc = hx.ckks_ptct_mac(ctx, dp, dc, level)
+    want = orc.ptct_mac(pts, cts, level)
+    assert np.array_equal(hx.to_host(acc), want)
+    # accumulate on top of an existing accumulator
+    acc2 = hx.ckks_ptct_mac(ctx, dp[:1], dc[:1], level, acc=acc, accumulate=True)
+    assert np.array_equal(hx.to_host(acc2), orc.ptct_mac(pts[:1], cts[:1], level, acc=want))
+
+
+@pytest.mark.parametrize("level", [6, 3, 1])
+def test_rescale_matches_oracle(ks_setup, level):
+    p, orc, ctx, *_ = ks_setup
+    ct = rand_ct(np.random.default_rng(60 + level), p.moduli, level, orc.N)
+    ct[0, level, :4] = (0, 1, p.moduli[level] // 2, p.moduli[level] // 2 + 1)   # around the centring threshold
+    out = hx.ckks_rescale(ctx, hx.from_host(ct), level)
+    assert np.array_equal(hx.to_host(out), orc.rescale(ct, level))
+
+
+@pytest.mark.parametrize("level", [6, 2, 0])
+def test_ctct_mul_relin_matches_oracle(ks_setup, level):
+    p, orc, ctx, s, s_ntt, rlk, d_rlk = ks_setup
+    rng = np.random.default_rng(70 + level)
+    a, b = rand_ct(rng, p.moduli, level, orc.N), rand_ct(rng, p.moduli, level, orc.N)
+    out = hx.ckks_ctct_mul_relin(ctx, hx.from_host(a), hx.from_host(b), level, d_rlk)
+    assert np.array_equal(hx.to_host(out), orc.ctct_mul_relin(a, b, rlk, level))
+    da = hx.from_host(a)
+    sq = hx.ckks_ctct_mul_relin(ctx, da, da, level, d_rlk)         # squaring: both operands the same buffer
+    assert np.array_equal(hx.to_host(sq), orc.ctct_mul_relin(a, a, rlk, level))
+
+
+# ----------------------------------------------------------------------------------- convolution
+def conv_case(name, level=None):
+    wl = CONFIGS[name]
+    p = wl.params()
+    orc, ctx = both(p)
+    level = p.num_q - 1 if level is None else level
+    s, s_ntt = orc.gen_secret(101)
+    img = image_batch(wl.batch, wl.c_in, wl.height, wl.width)
+    w = conv_weights(wl.c_out, wl.c_in, dist="uniform" if wl.c_in == 1 else "he_normal")
+    scale = 2.0 ** 40
+    cts = [orc.encrypt(orc.pack_channel(img, c), scale, level, s_ntt, 110 + c) for c in range(wl.c_in)]
+    offs = conv_tap_offsets(wl.width)
+    keys = {off: orc.gen_rotation_key(s, s_ntt, off, 200 + i) for i, off in enumerate(offs) if off}
+    masks, w_int = orc.conv_operands(w, wl.height, wl.width, wl.batch, level, 2.0 ** 28, p.moduli[level] / 2.0 ** 28)
+    dkeys = [hx.ckks_key_load(ctx, hx.from_host(keys[off]), hx.ckks_galois_element(ctx, off)) if off else None for off in offs]
+    outs = hx.he_conv_batched(ctx, wl.height, wl.width, wl.batch, level, [hx.from_host(c) for c in cts], dkeys,
+                              hx.from_host(masks), hx.from_host(w_residues(w_int, p.moduli, level)), wl.c_out)
+    return wl, p, orc, level, s_ntt, img, w, scale, cts, keys, masks, w_int, [hx.to_host(o) for o in outs]
+
+
+@pytest.mark.parametrize("name,level", [("cfg1_single_conv", None), ("cfg1_single_conv_k1", None), ("small_conv", None), ("small_conv", 2)])
+def test_he_conv_matches_oracle_and_float_conv(name, level):
+    wl, p, orc, level, s_ntt, img, w, scale, cts, keys, masks, w_int, outs = conv_case(name, level)
+    want = orc.he_conv(cts, level, wl.width, keys, masks, w_int)
+    ref = conv2d_reference(img, w)
+    for o in range(wl.c_out):
+        assert np.array_equal(outs[o], want[o]), f"output channel {o}"
+        if name.endswith("_k1"):
+            continue    # one special prime for 2-limb digits: limb parity only, decryption is noise
+        dec = orc.unpack_channel(orc.decrypt(outs[o], level - 1, s_ntt, scale), wl.batch, wl.height, wl.width)
+        assert np.abs(dec - ref[:, o]).max() < 1e-4
+
+
+def test_he_conv_equals_composition_of_exported_ops():
+    """he_conv_batched == rotate_hoisted + ptct_mac (with materialised weight plaintexts) + rescale,
+    all on the GPU: the factored weights are an exact identity."""
+    wl, p, orc, level, s_ntt, img, w, scale, cts, keys, masks, w_int, outs = conv_case("small_conv")
+    ctx = hx.Context(p)
+    offs = conv_tap_offsets(wl.width)
+    dkeys = [hx.ckks_key_load(ctx, hx.from_host(keys[off]), hx.ckks_galois_element(ctx, off)) if off else None for off in offs]
+    aligned = [hx.ckks_rotate_hoisted(ctx, hx.from_host(c), level, offs, dkeys, True) for c in cts]
+    for o in range(wl.c_out):
+        pts, terms = [], []
+        for c in range(wl.c_in):
+            for t in range(9):
+                pts.append(hx.from_host(orc.scalar_mul(masks[t], orc.scalar_residues(int(w_int[o, c, t]), level), level)))
+                terms.append(aligned[c][t])
+        acc = hx.ckks_ptct_mac(ctx, pts, terms, level)
+        assert np.array_equal(hx.to_host(hx.ckks_rescale(ctx, acc, level)), outs[o])
+
+
+# ------------------------------------------------------------------------------------ activation
+def test_poly_activation_matches_oracle():
+    wl = CONFIGS["small_block"]
+    p = wl.params()
+    orc, ctx = both(p)
+    level = p.num_q - 1
+    s, s_ntt = orc.gen_secret(301)
+    rlk = orc.gen_relin_key(s_ntt, 302)
+    x = np.random.default_rng(303).uniform(-1, 1, orc.n)
+    scale = 2.0 ** 50
+    ct = orc.encrypt(x, scale, level, s_ntt, 304)
+    plan = orc.act_schedule(level, scale)
+    want = orc.poly_activation(ct, level, plan["k"], rlk)
+    out = hx.he_poly_act_deg7(ctx, hx.from_host(ct), level, plan["k"], hx.ckks_key_load(ctx, hx.from_host(rlk), 0))
+    got = hx.to_host(out)
+    assert np.array_equal(got, want)
+    dec = orc.decrypt(got, plan["out_level"], s_ntt, plan["out_scale"])
+    assert np.abs(dec - activation_reference(x)).max() < 1e-3
+
+
+# ----------------------------------------------------------------------------------- error paths
+def test_error_codes(ks_setup):
+    p, orc, ctx, s, s_ntt, rlk, d_rlk = ks_setup
+    level = 3
+    ct = hx.from_host(rand_ct(np.random.default_rng(1), p.moduli, level, orc.N))
+    with pytest.raises(hx.CkksError) as e:
+        hx.ckks_keyswitch(ctx, ct[0], level, d_rlk, ws=hx.empty(16))
+    assert e.value.code == hx.binding.CKKS_ERR_WORKSPACE_TOO_SMALL
+    with pytest.raises(hx.CkksError) as e:
+        hx.ckks_keyswitch(ctx, ct[0], level, None)
+    assert e.value.code == hx.binding.CKKS_ERR_NO_KEY
+    with pytest.raises(hx.CkksError) as e:
+        hx.ckks_rescale(ctx, hx.empty(2, 1, orc.N), 0)
+    assert e.value.code == hx.binding.CKKS_ERR_LEVEL_MISMATCH
+    k1 = hx.ckks_key_load(ctx, hx.from_host(rlk), hx.ckks_galois_element(ctx, 1))
+    with pytest.raises(hx.CkksError) as e:                 # key of offset 1 offered for offset 2
+        hx.ckks_rotate_hoisted(ctx, ct, level, [2], [k1])
+    assert e.value.code == hx.binding.CKKS_ERR_NO_KEY
+    with pytest.raises(hx.CkksError) as e:                 # a rotation key is not a relinearisation key
+        hx.ckks_ctct_mul_relin(ctx, ct, ct, level, k1)
+    assert e.value.code == hx.binding.CKKS_ERR_NO_KEY
+    with pytest.raises(hx.CkksError) as e:                 # slot constraint m*b <= n
+        hx.he_conv_batched(ctx, 64, 64, 2, level, [ct], [None] * 9, hx.empty(9, level + 1, orc.N), hx.empty(1, 1, 9, level + 1), 1)
+    assert e.value.code == hx.binding.CKKS_ERR_INVALID_ARG
+    with pytest.raises(hx.CkksError) as e:
+        hx.ckks_ntt_fwd(ctx, hx.empty(1, 1, orc.N), [99])
+    assert e.value.code == hx.binding.CKKS_ERR_INVALID_ARG

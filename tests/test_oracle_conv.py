@@ -134,14 +134,13 @@ def test_he_conv_centre_only_kernel_is_scalar_multiple():
     assert np.abs(got - 0.375 * o.pack_channel(img, 0)).max() < 1e-5
 
 
-def test_he_conv_unhoisted_schedule_agrees_after_decryption():
+def test_he_conv_unhoisted_schedule_agrees():
     wl, p, o, level, s, s_ntt, img, w, scale, cts, keys = _conv_setup("cfg1_single_conv", 3000)
     delta_m = 2.0 ** 28
     M, w_int = o.conv_operands(w, wl.height, wl.width, wl.batch, level, delta_m, p.moduli[level] / delta_m)
     a = o.he_conv(cts, level, wl.width, keys, M, w_int, hoisted=True)[0]
     b = o.he_conv(cts, level, wl.width, keys, M, w_int, hoisted=False)[0]
-    assert not np.array_equal(a, b)
-    assert np.abs(o.decrypt(a, level - 1, s_ntt, scale) - o.decrypt(b, level - 1, s_ntt, scale)).max() < 1e-5
+    assert np.array_equal(a, b)
 
 
 def test_activation_polynomial_pins():

@@ -16,8 +16,8 @@ def coeff_form(o, poly, mod_idx):
 
 @pytest.mark.parametrize("level", [2, 1, 0])
 def test_modup_is_c_plus_small_multiple_of_digit_modulus(tiny_params, level):
-    """Extended digit j == c + u*Q_j as integers with 0 <= u < |digit| (uncorrected extension),
-    for the full digit {q0,q1} and the ragged digit {q2}, at every level."""
+    """Extended digit j == c + u*Q_j as integers with |d_j| <= |digit| * Q_j / 2 (centred,
+    uncorrected extension), for the full digit {q0,q1} and the ragged digit {q2}, at every level."""
     p = tiny_params
     o = Oracle(p)
     rng = np.random.default_rng(10 + level)
@@ -31,18 +31,22 @@ def test_modup_is_c_plus_small_multiple_of_digit_modulus(tiny_params, level):
         lo, hi = j * o.alpha, min((j + 1) * o.alpha, level + 1)
         Qj = prod(p.moduli[lo:hi])
         dj = coeff_form(o, d[j], ext)
+        E = prod(ext_mod)
+        seen_u = set()
         for x in range(o.N):
-            cx = crt([c_coeff[i, x] for i in range(lo, hi)], p.moduli[lo:hi])
-            dx = crt(dj[:, x], ext_mod)
+            cx = centred(crt([c_coeff[i, x] for i in range(lo, hi)], p.moduli[lo:hi]), Qj)
+            dx = centred(crt(dj[:, x], ext_mod), E)
             u, rem = divmod(dx - cx, Qj)
-            assert rem == 0 and 0 <= u < hi - lo
+            assert rem == 0 and 2 * abs(dx) <= (hi - lo) * Qj
+            seen_u.add(u)
+        assert seen_u <= {-1, 0, 1} and (hi - lo == 1 and seen_u == {0} or hi - lo > 1)
         # the digit's own limbs are untouched
         assert np.array_equal(d[j, lo:hi], c[lo:hi])
 
 
 @pytest.mark.parametrize("level", [2, 0])
 def test_moddown_is_floor_division_by_P_up_to_small_error(tiny_params, level):
-    """u == floor(V/P) - e (mod Q_level) with 0 <= e < k."""
+    """u == round(V/P) - e (mod Q_level) with |e| <= k/2: |V - P*u| <= (k+1)*P/2, both signs seen."""
     p = tiny_params
     o = Oracle(p)
     ext = o.ext_moduli_idx(level)
@@ -54,11 +58,14 @@ def test_moddown_is_floor_division_by_P_up_to_small_error(tiny_params, level):
     Q = prod(p.moduli[:level + 1])
     vc = coeff_form(o, v, ext)
     uc = coeff_form(o, u, list(range(level + 1)))
+    signs = set()
     for x in range(o.N):
         V = crt(vc[:, x], ext_mod)
         U = crt(uc[:, x], p.moduli[:level + 1])
-        e = (V // P - U) % Q
-        assert 0 <= e < p.num_p
+        U = min((U, U - Q, U + Q), key=lambda t: abs(V - P * t))   # representative nearest to V/P
+        assert 2 * abs(V - P * U) <= (p.num_p + 1) * P
+        signs.add(V - P * U > 0)
+    assert signs == {True, False}
 
 
 @pytest.mark.parametrize("level", [2, 1])
@@ -152,7 +159,8 @@ def test_rotation_is_left_slot_roll_both_orders(cfg1_params, offset):
     assert np.abs(du - want).max() < 1e-5
     assert np.abs(dh - want).max() < 1e-5
     assert np.abs(du - dh).max() < 1e-5
-    assert not np.array_equal(un, ho)  # different integers, same message
+    # centred digits commute with the automorphism's sign flips: the two orders agree exactly
+    assert np.array_equal(un, ho)
 
 
 def test_rotate_there_and_back(cfg1_params):
