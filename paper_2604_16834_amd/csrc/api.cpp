@@ -48,9 +48,10 @@ PolyList range_list(u32 first_pos, u32 count, u32 first_mod) {
 }
 
 // ---- workspace sizes ---------------------------------------------------------------------------
-size_t ws_keyswitch(const ckks_ctx* c, u32 level) {
+// rb = how many key switches share one pass of the ModDown kernels (1..KS_MAX_BATCH)
+size_t ws_keyswitch(const ckks_ctx* c, u32 level, u32 rb = 1) {
     const size_t N = c->N, L1 = level + 1, E = c->ext_limbs(level), beta = c->live_digits(level);
-    return blk(L1 * N) + blk(beta * E * N) + blk(2 * E * N) + blk(2 * L1 * N);
+    return blk(L1 * N) + blk(beta * E * N) + blk(rb * 2 * E * N) + blk(rb * 2 * L1 * N);
 }
 size_t ws_rescale(const ckks_ctx* c, u32 level) { return blk(2 * (size_t)c->N) + blk(2 * (size_t)level * c->N); }
 size_t ws_ctct(const ckks_ctx* c, u32 level) { return 3 * blk((size_t)(level + 1) * c->N) + ws_keyswitch(c, level); }
@@ -58,12 +59,12 @@ size_t ws_ctct(const ckks_ctx* c, u32 level) { return 3 * blk((size_t)(level + 1
 struct KsBuffers {
     u64 *y, *digits, *v, *w;
 };
-bool carve_ks(const ckks_ctx* c, u32 level, Arena& ar, KsBuffers& b) {
+bool carve_ks(const ckks_ctx* c, u32 level, Arena& ar, KsBuffers& b, u32 rb = 1) {
     const size_t N = c->N, L1 = level + 1, E = c->ext_limbs(level), beta = c->live_digits(level);
     b.y = ar.take(L1 * N);
     b.digits = ar.take(beta * E * N);
-    b.v = ar.take(2 * E * N);
-    b.w = ar.take(2 * L1 * N);
+    b.v = ar.take(rb * 2 * E * N);
+    b.w = ar.take(rb * 2 * L1 * N);
     return ar.ok();
 }
 
@@ -91,17 +92,19 @@ int run_modup(const ckks_ctx* c, u32 level, const u64* d_c, const KsBuffers& b, 
     return CKKS_OK;
 }
 
-// Inner product with the key (digits read through sigma_g) and ModDown; adds add0/add1 (read through
-// sigma_g as well) to the two output components.  out [2][level+1][N].
-int run_inner_moddown(const ckks_ctx* c, u32 level, const KsBuffers& b, const u64* d_key, u32 g, const u64* add0,
-                      const u64* add1, u64* out, hipStream_t st) {
+// n <= KS_MAX_BATCH key switches of the same extended digits: inner product with each key (digits read
+// through sigma_g of the item), then one pass of every ModDown kernel over the whole batch.  items[r]
+// says what is added to / multiplied into the r-th result and where it goes ([2][level+1][N]).
+int run_inner_moddown(const ckks_ctx* c, u32 level, const KsBuffers& b, u32 n, const u64* const* d_keys, const FinalItem* items,
+                      hipStream_t st) {
     const u32 L1 = level + 1, E = c->ext_limbs(level), k = c->num_p;
-    HIP_TRY(launch_key_inner(c, level, b.digits, d_key, g, b.v, st));
-    // P-part of both components to coefficient form, in place
-    HIP_TRY(launch_ntt(c, true, b.v, E, b.v, E, range_list(L1, k, c->num_q), 2, st));
-    HIP_TRY(launch_moddown_conv(c, level, b.v, b.w, st));
-    HIP_TRY(launch_ntt(c, false, b.w, L1, b.w, L1, range_list(0, L1, 0), 2, st));
-    HIP_TRY(launch_moddown_final(c, level, b.v, b.w, add0, add1, g, out, st));
+    const size_t N = c->N;
+    for (u32 r = 0; r < n; r++) HIP_TRY(launch_key_inner(c, level, b.digits, d_keys[r], items[r].g, b.v + (size_t)r * 2 * E * N, st));
+    // P-part of every component to coefficient form, in place
+    HIP_TRY(launch_ntt(c, true, b.v, E, b.v, E, range_list(L1, k, c->num_q), 2 * n, st));
+    HIP_TRY(launch_moddown_conv(c, level, b.v, b.w, 2 * n, st));
+    HIP_TRY(launch_ntt(c, false, b.w, L1, b.w, L1, range_list(0, L1, 0), 2 * n, st));
+    HIP_TRY(launch_moddown_final(c, level, b.v, b.w, items, n, st));
     return CKKS_OK;
 }
 
@@ -131,7 +134,8 @@ int run_ctct(const ckks_ctx* c, u32 level, const u64* a, size_t a_cstride, const
     HIP_TRY(launch_tensor(c, level, a, a_cstride, b, b_cstride, d0, d1, d2, st));
     int rc = run_modup(c, level, d2, kb, st);
     if (rc) return rc;
-    return run_inner_moddown(c, level, kb, d_rlk, 1, d0, d1, out, st);
+    const FinalItem item = {d0, d1, nullptr, out, 1, 0};
+    return run_inner_moddown(c, level, kb, 1, &d_rlk, &item, st);
 }
 
 bool level_ok(const ckks_ctx* c, u32 level) { return level < c->num_q; }
@@ -145,7 +149,10 @@ size_t ckks_workspace_bytes(const ckks_ctx* c, int op, uint32_t level, uint32_t 
     const size_t N = c->N, L1 = level + 1;
     switch (op) {
         case CKKS_OP_KEYSWITCH: return c->dnum ? ws_keyswitch(c, level) : 0;
-        case CKKS_OP_ROTATE: return c->dnum ? ws_keyswitch(c, level) + blk(L1 * N) : 0;
+        case CKKS_OP_ROTATE: {
+            const u32 rb = count < 1 ? 1 : (count > KS_MAX_BATCH ? KS_MAX_BATCH : count);
+            return c->dnum ? ws_keyswitch(c, level, rb) + blk(L1 * N) : 0;
+        }
         case CKKS_OP_RESCALE: return level >= 1 ? ws_rescale(c, level) : 0;
         case CKKS_OP_CTCT_MUL_RELIN: return c->dnum ? ws_ctct(c, level) : 0;
         case CKKS_OP_POLY_ACT: {
@@ -163,8 +170,8 @@ size_t ckks_workspace_bytes(const ckks_ctx* c, int op, uint32_t level, uint32_t 
 size_t he_conv_workspace_bytes(const ckks_ctx* c, const he_conv_desc* d) {
     if (!c || !d || !c->dnum || !level_ok(c, d->level) || d->level < 1) return 0;
     const size_t N = c->N, L1 = d->level + 1;
-    return ws_keyswitch(c, d->level) + blk(2 * L1 * N) + blk((size_t)d->c_in * 9 * 2 * L1 * N) + blk((size_t)d->c_out * 2 * L1 * N) +
-           ws_rescale(c, d->level);
+    return ws_keyswitch(c, d->level, KS_MAX_BATCH) + blk((size_t)d->c_in * 9 * 2 * L1 * N) + blk((size_t)d->c_out * 2 * L1 * N) +
+           blk(weighted_sum_scratch_elems(c, d->level, d->c_in * 9, d->c_out)) + ws_rescale(c, d->level);
 }
 
 uint32_t ckks_galois_element(const ckks_ctx* c, int32_t offset) {
@@ -237,7 +244,8 @@ int ckks_keyswitch(const ckks_ctx* c, const uint64_t* d_c, uint32_t level, const
     hipStream_t st = (hipStream_t)stream;
     int rc = run_modup(c, level, (const u64*)d_c, b, st);
     if (rc) return rc;
-    return run_inner_moddown(c, level, b, key->d_key, 1, nullptr, nullptr, (u64*)d_out, st);
+    const FinalItem item = {nullptr, nullptr, nullptr, (u64*)d_out, 1, 0};
+    return run_inner_moddown(c, level, b, 1, &key->d_key, &item, st);
 }
 
 int ckks_rotate_hoisted(const ckks_ctx* c, const uint64_t* d_ct, uint32_t level, const int32_t* h_offsets, uint32_t n_rot,
@@ -258,11 +266,15 @@ int ckks_rotate_hoisted(const ckks_ctx* c, const uint64_t* d_ct, uint32_t level,
         if (!keys || !keys[t]) return set_err(c, CKKS_ERR_NO_KEY, "rotation key missing");
         if (keys[t]->galois_elt != g) return set_err(c, CKKS_ERR_NO_KEY, "rotation key was made for another offset");
     }
+    // hoisted rotations go through the ModDown kernels in batches of up to KS_MAX_BATCH
+    u32 n_keyed = 0;
+    for (u32 t = 0; t < n_rot; t++) n_keyed += ckks_galois_element(c, h_offsets[t]) != 1;
+    const u32 rb = hoisted ? (n_keyed < KS_MAX_BATCH ? (n_keyed ? n_keyed : 1) : KS_MAX_BATCH) : 1;
     Arena ar(d_ws, ws_bytes);
     KsBuffers b = {nullptr, nullptr, nullptr, nullptr};
     u64* pc1 = nullptr;
     if (any) {
-        if (!carve_ks(c, level, ar, b)) return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for rotation");
+        if (!carve_ks(c, level, ar, b, rb)) return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for rotation");
         if (!hoisted) {
             pc1 = ar.take(L1 * N);
             if (!ar.ok()) return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for rotation");
@@ -276,6 +288,9 @@ int ckks_rotate_hoisted(const ckks_ctx* c, const uint64_t* d_ct, uint32_t level,
         int rc = run_modup(c, level, c1, b, st);
         if (rc) return rc;
     }
+    FinalItem items[KS_MAX_BATCH];
+    const u64* bkeys[KS_MAX_BATCH];
+    u32 nb = 0;
     for (u32 t = 0; t < n_rot; t++) {
         const u32 g = ckks_galois_element(c, h_offsets[t]);
         u64* out = (u64*)h_d_outs[t];
@@ -284,20 +299,30 @@ int ckks_rotate_hoisted(const ckks_ctx* c, const uint64_t* d_ct, uint32_t level,
             continue;
         }
         if (hoisted) {
-            int rc = run_inner_moddown(c, level, b, keys[t]->d_key, g, c0, nullptr, out, st);
-            if (rc) return rc;
+            items[nb] = FinalItem{c0, nullptr, nullptr, out, g, 0};
+            bkeys[nb] = keys[t]->d_key;
+            if (++nb == rb) {
+                int rc = run_inner_moddown(c, level, b, nb, bkeys, items, st);
+                if (rc) return rc;
+                nb = 0;
+            }
         } else {
             HIP_TRY(launch_automorph(c, (u32)L1, c1, g, pc1, st));
             int rc = run_modup(c, level, pc1, b, st);
             if (rc) return rc;
-            // digits already belong to sigma_g(c1): no gather in the inner product, gather only on c0
-            HIP_TRY(launch_key_inner(c, level, b.digits, keys[t]->d_key, 1, b.v, st));
+            // the digits already belong to sigma_g(c1): no gather in the inner product, only on c0
             const u32 E = c->ext_limbs(level), k = c->num_p;
+            HIP_TRY(launch_key_inner(c, level, b.digits, keys[t]->d_key, 1, b.v, st));
             HIP_TRY(launch_ntt(c, true, b.v, E, b.v, E, range_list((u32)L1, k, c->num_q), 2, st));
-            HIP_TRY(launch_moddown_conv(c, level, b.v, b.w, st));
+            HIP_TRY(launch_moddown_conv(c, level, b.v, b.w, 2, st));
             HIP_TRY(launch_ntt(c, false, b.w, L1, b.w, L1, range_list(0, (u32)L1, 0), 2, st));
-            HIP_TRY(launch_moddown_final(c, level, b.v, b.w, c0, nullptr, g, out, st));
+            const FinalItem item = {c0, nullptr, nullptr, out, g, 0};
+            HIP_TRY(launch_moddown_final(c, level, b.v, b.w, &item, 1, st));
         }
+    }
+    if (nb) {
+        int rc = run_inner_moddown(c, level, b, nb, bkeys, items, st);
+        if (rc) return rc;
     }
     return CKKS_OK;
 }
@@ -365,33 +390,41 @@ int he_conv_batched(const ckks_ctx* c, const he_conv_desc* d, const uint64_t* co
 
     Arena ar(d_ws, ws_bytes);
     KsBuffers b;
-    bool ok = carve_ks(c, level, ar, b);
-    u64* rot = ar.take(ct_elems);
+    bool ok = carve_ks(c, level, ar, b, KS_MAX_BATCH);
     u64* xs = ar.take((size_t)d->c_in * 9 * ct_elems);
     u64* acc = ar.take((size_t)d->c_out * ct_elems);
+    u64* wscratch = ar.take(weighted_sum_scratch_elems(c, level, d->c_in * 9, d->c_out));
     if (!ok || !ar.ok() || ar.used + ws_rescale(c, level) > ar.cap)
         return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for the convolution");
     hipStream_t st = (hipStream_t)stream;
 
-    // input alignment: nine aligned copies of every input channel, each times its tap mask
+    // input alignment: nine aligned copies of every input channel, each times its tap mask; the eight
+    // rotations of a channel share the decomposition and go through the ModDown kernels as one batch
     for (u32 ci = 0; ci < d->c_in; ci++) {
         const u64* ct = (const u64*)h_d_in[ci];
         int rc = run_modup(c, level, ct + L1 * N, b, st);
         if (rc) return rc;
+        FinalItem items[KS_MAX_BATCH];
+        const u64* bkeys[KS_MAX_BATCH];
+        u32 nb = 0;
         for (u32 t = 0; t < 9; t++) {
             const u64* mask = (const u64*)d_tap_masks + (size_t)t * L1 * N;
             u64* x = xs + ((size_t)ci * 9 + t) * ct_elems;
             if (gs[t] == 1) {
                 HIP_TRY(launch_mask_mul(c, level, mask, ct, x, st));
-            } else {
-                rc = run_inner_moddown(c, level, b, rot_keys[t]->d_key, gs[t], ct, nullptr, rot, st);
-                if (rc) return rc;
-                HIP_TRY(launch_mask_mul(c, level, mask, rot, x, st));
+                continue;
+            }
+            items[nb] = FinalItem{ct, nullptr, mask, x, gs[t], 0};
+            bkeys[nb] = rot_keys[t]->d_key;
+            if (++nb == KS_MAX_BATCH) {
+                if ((rc = run_inner_moddown(c, level, b, nb, bkeys, items, st))) return rc;
+                nb = 0;
             }
         }
+        if (nb && (rc = run_inner_moddown(c, level, b, nb, bkeys, items, st))) return rc;
     }
     // convolution evaluation: integer-weighted sum over (input channel, tap) for every output channel
-    HIP_TRY(launch_weighted_sum(c, level, xs, d->c_in * 9, (const u64*)d_w_res, d->c_out, acc, st));
+    HIP_TRY(launch_weighted_sum(c, level, xs, d->c_in * 9, (const u64*)d_w_res, d->c_out, acc, wscratch, st));
     for (u32 o = 0; o < d->c_out; o++) {
         Arena tmp(ar.base + ar.used, ar.cap - ar.used);
         int rc = run_rescale(c, level, acc + (size_t)o * ct_elems, L1 * N, (u64*)h_d_out[o], tmp, st);

@@ -61,9 +61,7 @@ extern "C" void ckks_ctx_destroy(ckks_ctx* c) {
     if (!c) return;
     (void)hipFree(c->d_mc);
     (void)hipFree(c->d_tw);
-    (void)hipFree(c->d_tw_sh);
     (void)hipFree(c->d_itw);
-    (void)hipFree(c->d_itw_sh);
     (void)hipFree(c->d_modup);
     (void)hipFree(c->d_moddown);
     (void)hipFree(c->d_rescale);
@@ -105,11 +103,12 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
     c->log_lo = p->log_n < CKKS_TILE_LOG ? p->log_n : CKKS_TILE_LOG;
     c->log_hi = p->log_n - c->log_lo;
     c->lazy_terms = 1u << (lazy_log > 12 ? 12 : lazy_log);
+    c->small_q = bmax <= 50;
     c->mod.assign(p->moduli, p->moduli + M);
     c->psi.assign(p->psi, p->psi + M);
 
     c->mc.resize(M);
-    std::vector<u64> tw((size_t)M * N), tw_sh((size_t)M * N), itw((size_t)M * N), itw_sh((size_t)M * N);
+    std::vector<TwPair> tw((size_t)M * N), itw((size_t)M * N);
     for (u32 t = 0; t < M; t++) {
         const u64 q = c->mod[t];
         ModConst& m = c->mc[t];
@@ -129,8 +128,8 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
         for (u32 i = 0; i < N; i++) {
             const u32 r = h_bitrev(i, p->log_n);
             const size_t o = (size_t)t * N + i;
-            tw[o] = pw[r]; tw_sh[o] = h_shoup(pw[r], q);
-            itw[o] = ipw[r]; itw_sh[o] = h_shoup(ipw[r], q);
+            tw[o].w = pw[r]; tw[o].s = h_shoup(pw[r], q);
+            itw[o].w = ipw[r]; itw[o].s = h_shoup(ipw[r], q);
         }
     }
 
@@ -206,9 +205,7 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
     hipError_t e = hipSuccess;
     if (e == hipSuccess) e = upload(c->mc, &c->d_mc);
     if (e == hipSuccess) e = upload(tw, &c->d_tw);
-    if (e == hipSuccess) e = upload(tw_sh, &c->d_tw_sh);
     if (e == hipSuccess) e = upload(itw, &c->d_itw);
-    if (e == hipSuccess) e = upload(itw_sh, &c->d_itw_sh);
     if (e == hipSuccess) e = upload(modup, &c->d_modup);
     if (e == hipSuccess) e = upload(moddown, &c->d_moddown);
     if (e == hipSuccess) e = upload(resc, &c->d_rescale);

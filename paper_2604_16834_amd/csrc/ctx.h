@@ -21,6 +21,11 @@ struct PolyList {
     unsigned char mod[CKKS_MAX_MODULI];
 };
 
+// a constant multiplier and its Shoup companion floor(w * 2^64 / q), loaded as one 16-byte word
+struct __attribute__((aligned(16))) TwPair {
+    u64 w, s;
+};
+
 // kernel classes, for the optional per-kernel timing (ckks_prof_begin / ckks_prof_end)
 enum KernelId {
     K_NTT_FWD_HI = 0, K_NTT_FWD_LO, K_NTT_INV_LO, K_NTT_INV_HI, K_MODUP_CONV, K_KEY_INNER, K_MODDOWN_CONV, K_MODDOWN_FINAL,
@@ -36,6 +41,20 @@ struct ProfState {
     double ops[K_COUNT] = {0};    // modular multiplications (butterflies, multiply-adds) of the recorded launches
 };
 
+// One key switch of a batch, as its last kernel sees it (see moddown_final_kernel).
+#define KS_MAX_BATCH 8
+struct FinalItem {
+    const u64* add0;
+    const u64* add1;
+    const u64* mask;
+    u64* out;
+    u32 g;
+    u32 pad;
+};
+struct FinalBatch {
+    FinalItem it[KS_MAX_BATCH];
+};
+
 struct ckks_key {
     const u64* d_key;
     u32 galois_elt;
@@ -44,16 +63,15 @@ struct ckks_key {
 struct ckks_ctx {
     u32 log_n, N, num_q, num_p, dnum, alpha, M;
     u32 log_lo, log_hi;  // N = 2^log_hi blocks-of-stride x 2^log_lo contiguous
+    bool small_q;        // every modulus is below 2^50: carry-free 25-bit-split accumulation applies
     u32 lazy_terms;      // how many products of two residues may be summed in 128 bits before a reduction
     std::vector<u64> mod, psi;
     std::vector<ModConst> mc;
 
     // device tables
     ModConst* d_mc = nullptr;         // [M]
-    u64* d_tw = nullptr;              // [M][N]  psi^bitrev(i)
-    u64* d_tw_sh = nullptr;           // Shoup companions
-    u64* d_itw = nullptr;             // [M][N]  psi^-bitrev(i)
-    u64* d_itw_sh = nullptr;
+    TwPair* d_tw = nullptr;           // [M][N]  psi^bitrev(i) with its Shoup companion
+    TwPair* d_itw = nullptr;          // [M][N]  psi^-bitrev(i) with its Shoup companion
     u64* d_modup = nullptr;           // per level, per digit: see modup_digit_stride()
     u64* d_moddown = nullptr;         // phat_inv[k], phat_inv_sh[k], phat_q[k][num_q], pinv[num_q], pinv_sh[num_q], negp[num_q]
     u64* d_rescale = nullptr;         // [num_q][num_q][3]: (q_l^-1 mod q_i, its Shoup companion, q_l mod q_i)
@@ -101,9 +119,8 @@ hipError_t launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, size_t sr
 // keyswitch.hip
 hipError_t launch_modup_conv(const ckks_ctx* c, u32 level, u32 j, const u64* y, const u64* c_in, u64* digit, hipStream_t st);
 hipError_t launch_key_inner(const ckks_ctx* c, u32 level, const u64* digits, const u64* key, u32 g, u64* v, hipStream_t st);
-hipError_t launch_moddown_conv(const ckks_ctx* c, u32 level, const u64* v, u64* w, hipStream_t st);
-hipError_t launch_moddown_final(const ckks_ctx* c, u32 level, const u64* v, const u64* w, const u64* add0, const u64* add1,
-                                u32 g, u64* out, hipStream_t st);
+hipError_t launch_moddown_conv(const ckks_ctx* c, u32 level, const u64* v, u64* w, u32 batch, hipStream_t st);
+hipError_t launch_moddown_final(const ckks_ctx* c, u32 level, const u64* v, const u64* w, const FinalItem* items, u32 n, hipStream_t st);
 // pointwise.hip
 hipError_t launch_automorph(const ckks_ctx* c, u32 n_polys, const u64* in, u32 g, u64* out, hipStream_t st);
 hipError_t launch_copy(const u64* in, u64* out, size_t n, hipStream_t st);
@@ -114,7 +131,8 @@ hipError_t launch_rescale_final(const ckks_ctx* c, u32 level, const u64* ct, siz
 hipError_t launch_tensor(const ckks_ctx* c, u32 level, const u64* a, size_t a_cstride, const u64* b, size_t b_cstride, u64* d0,
                          u64* d1, u64* d2, hipStream_t st);
 hipError_t launch_mask_mul(const ckks_ctx* c, u32 level, const u64* mask, const u64* ct, u64* out, hipStream_t st);
+size_t weighted_sum_scratch_elems(const ckks_ctx* c, u32 level, u32 n_terms, u32 c_out);
 hipError_t launch_weighted_sum(const ckks_ctx* c, u32 level, const u64* xs, u32 n_terms, const u64* w_res, u32 c_out, u64* acc,
-                               hipStream_t st);
+                               u64* scratch, hipStream_t st);
 hipError_t launch_lincomb2(const ckks_ctx* c, u32 level, const u64* a, size_t a_cstride, const u64* ka, const u64* b,
                            size_t b_cstride, const u64* kb, const u64* add, u64* out, hipStream_t st);

@@ -61,9 +61,50 @@ __global__ __launch_bounds__(KS_THREADS) void modup_conv_kernel(const u64* __res
     }
 }
 
+// ModUp for moduli below 2^50: carry-free 25-bit-split accumulation (three multiply-adds per term)
+__global__ __launch_bounds__(KS_THREADS) void modup_conv50_kernel(const u64* __restrict__ y, const u64* __restrict__ c_in,
+                                                                  u64* __restrict__ digit, const u64* __restrict__ tab,
+                                                                  const ModConst* __restrict__ mc, u32 N, u32 level, u32 num_q,
+                                                                  u32 lo, u32 nd, u32 alpha, u32 M, u32 E) {
+    const u32 x = blockIdx.x * KS_THREADS + threadIdx.x;
+    if (x >= N) return;
+    Split50 yv[KS_MAX_DIGIT];
+    u32 n_neg = 0;
+#pragma unroll
+    for (u32 a = 0; a < KS_MAX_DIGIT; a++)
+        if (a < nd) {
+            const u64 qa = mc[lo + a].q;
+            const u64 v = mul_shoup(y[(size_t)a * N + x], tab[a], tab[alpha + a], qa);
+            n_neg += v > (qa >> 1) ? 1 : 0;
+            yv[a] = split50(v);
+        }
+    const u64* negq = tab + (size_t)alpha * (2 + M);
+    const u32 e0 = blockIdx.y * MODUP_LIMBS_PER_BLOCK;
+    for (u32 e = e0; e < e0 + MODUP_LIMBS_PER_BLOCK && e < E; e++) {
+        const u32 t = e <= level ? e : num_q + (e - level - 1);
+        if (t >= lo && t < lo + nd) {
+            digit[(size_t)e * N + x] = c_in[(size_t)t * N + x];
+            continue;
+        }
+        Acc50 acc = {0, 0, 0};
+#pragma unroll
+        for (u32 a = 0; a < KS_MAX_DIGIT; a++)
+            if (a < nd) acc50_mad(acc, yv[a], split50(tab[2 * alpha + (size_t)a * M + e]));
+        U128 v = acc50_value(acc);
+        acc_wide(v, n_neg, negq[e]);
+        digit[(size_t)e * N + x] = barrett_reduce(v, mc[t]);
+    }
+}
+
 hipError_t launch_modup_conv(const ckks_ctx* c, u32 level, u32 j, const u64* y, const u64* c_in, u64* digit, hipStream_t st) {
     const u32 E = c->ext_limbs(level), lo = c->digit_lo(j), nd = c->digit_hi(j, level) - lo;
     dim3 grid((c->N + KS_THREADS - 1) / KS_THREADS, (E + MODUP_LIMBS_PER_BLOCK - 1) / MODUP_LIMBS_PER_BLOCK);
+    if (c->small_q) {
+        ProfScope ps__(c, K_MODUP_CONV, st, 8.0 * c->N * (2.0 * nd + E), (double)c->N * nd * (1.0 + E - nd));
+        hipLaunchKernelGGL(modup_conv50_kernel, grid, dim3(KS_THREADS), 0, st, y, c_in, digit, c->modup_table(level, j), c->d_mc,
+                           c->N, level, c->num_q, lo, nd, c->alpha, c->M, E);
+        return hipGetLastError();
+    }
     { ProfScope ps__(c, K_MODUP_CONV, st, 8.0 * c->N * (2.0 * nd + E), (double)c->N * nd * (1.0 + E - nd)); hipLaunchKernelGGL(modup_conv_kernel, grid, dim3(KS_THREADS), 0, st, y, c_in, digit, c->modup_table(level, j), c->d_mc,
                        c->N, level, c->num_q, lo, nd, c->alpha, c->M, E); }
     return hipGetLastError();
@@ -134,41 +175,90 @@ __global__ __launch_bounds__(KS_THREADS) void moddown_conv_kernel(const u64* __r
     }
 }
 
-hipError_t launch_moddown_conv(const ckks_ctx* c, u32 level, const u64* v, u64* w, hipStream_t st) {
-    dim3 grid((c->N + KS_THREADS - 1) / KS_THREADS, (level + 1 + MODDOWN_LIMBS_PER_BLOCK - 1) / MODDOWN_LIMBS_PER_BLOCK, 2);
-    { ProfScope ps__(c, K_MODDOWN_CONV, st, 16.0 * c->N * (c->num_p + level + 1.0), 2.0 * c->N * c->num_p * (level + 2.0)); hipLaunchKernelGGL(moddown_conv_kernel, grid, dim3(KS_THREADS), 0, st, v, w, c->d_moddown, c->d_mc, c->N, level,
+__global__ __launch_bounds__(KS_THREADS) void moddown_conv50_kernel(const u64* __restrict__ v, u64* __restrict__ w,
+                                                                    const u64* __restrict__ tab, const ModConst* __restrict__ mc,
+                                                                    u32 N, u32 level, u32 num_q, u32 k, u32 E) {
+    const u32 x = blockIdx.x * KS_THREADS + threadIdx.x;
+    if (x >= N) return;
+    const u32 comp = blockIdx.z;
+    Split50 z[KS_MAX_DIGIT];
+    u32 n_neg = 0;
+#pragma unroll
+    for (u32 a = 0; a < KS_MAX_DIGIT; a++)
+        if (a < k) {
+            const u64 pa = mc[num_q + a].q;
+            const u64 zv = mul_shoup(v[((size_t)comp * E + level + 1 + a) * N + x], tab[a], tab[k + a], pa);
+            n_neg += zv > (pa >> 1) ? 1 : 0;
+            z[a] = split50(zv);
+        }
+    const u64* phat_q = tab + 2 * k;
+    const u64* negp = tab + 2 * k + (size_t)k * num_q + 2 * num_q;
+    const u32 i0 = blockIdx.y * MODDOWN_LIMBS_PER_BLOCK;
+    for (u32 i = i0; i < i0 + MODDOWN_LIMBS_PER_BLOCK && i <= level; i++) {
+        Acc50 acc = {0, 0, 0};
+#pragma unroll
+        for (u32 a = 0; a < KS_MAX_DIGIT; a++)
+            if (a < k) acc50_mad(acc, z[a], split50(phat_q[(size_t)a * num_q + i]));
+        U128 s = acc50_value(acc);
+        acc_wide(s, n_neg, negp[i]);
+        w[((size_t)comp * (level + 1) + i) * N + x] = barrett_reduce(s, mc[i]);
+    }
+}
+
+hipError_t launch_moddown_conv(const ckks_ctx* c, u32 level, const u64* v, u64* w, u32 batch, hipStream_t st) {
+    dim3 grid((c->N + KS_THREADS - 1) / KS_THREADS, (level + 1 + MODDOWN_LIMBS_PER_BLOCK - 1) / MODDOWN_LIMBS_PER_BLOCK, batch);
+    if (c->small_q) {
+        ProfScope ps__(c, K_MODDOWN_CONV, st, 8.0 * batch * c->N * (c->num_p + level + 1.0), 1.0 * batch * c->N * c->num_p * (level + 2.0));
+        hipLaunchKernelGGL(moddown_conv50_kernel, grid, dim3(KS_THREADS), 0, st, v, w, c->d_moddown, c->d_mc, c->N, level, c->num_q,
+                           c->num_p, c->ext_limbs(level));
+        return hipGetLastError();
+    }
+    { ProfScope ps__(c, K_MODDOWN_CONV, st, 8.0 * batch * c->N * (c->num_p + level + 1.0), 1.0 * batch * c->N * c->num_p * (level + 2.0)); hipLaunchKernelGGL(moddown_conv_kernel, grid, dim3(KS_THREADS), 0, st, v, w, c->d_moddown, c->d_mc, c->N, level,
                        c->num_q, c->num_p, c->ext_limbs(level)); }
     return hipGetLastError();
 }
 
-// ---- ModDown, last step: out[comp][i] = (v[comp][i] - w[comp][i]) * P^-1 (+ addend) --------------
-// add0 / add1: optional polynomials [level+1][N] added to component 0 / 1; when g != 1 the addend
-// is read through the sigma_g gather (Rot: c0' = sigma_g(c0) + u0).
+// ---- ModDown, last step, for a batch of key switches -------------------------------------------
+// out_r[comp][i] = ((v_r[comp][i] - w_r[comp][i]) * P^-1 + addend) * mask, r < n (grid.z = 2n).
+// add0 / add1: optional polynomials [level+1][N] added to component 0 / 1; when g != 1 the addend is
+// read through the sigma_g gather (Rot: c0' = sigma_g(c0) + u0).  mask: optional plaintext
+// [level+1][N] multiplied into both components (the tap's validity mask of the convolution).
 __global__ __launch_bounds__(KS_THREADS) void moddown_final_kernel(const u64* __restrict__ v, const u64* __restrict__ w,
-                                                                   const u64* __restrict__ add0, const u64* __restrict__ add1,
-                                                                   u64* __restrict__ out, const u64* __restrict__ tab,
+                                                                   FinalBatch B, const u64* __restrict__ tab,
                                                                    const ModConst* __restrict__ mc, u32 log_n, u32 level,
-                                                                   u32 num_q, u32 k, u32 E, u32 g) {
+                                                                   u32 num_q, u32 k, u32 E) {
     const u32 N = 1u << log_n;
     const u32 x = blockIdx.x * KS_THREADS + threadIdx.x;
     if (x >= N) return;
-    const u32 i = blockIdx.y, comp = blockIdx.z;
-    const u64 q = mc[i].q;
+    const u32 i = blockIdx.y, b = blockIdx.z, comp = b & 1;
+    const FinalItem it = B.it[b >> 1];
+    const ModConst m = mc[i];
     const u64* pinv = tab + 2 * k + (size_t)k * num_q;
-    u64 d = sub_mod(v[((size_t)comp * E + i) * N + x], w[((size_t)comp * (level + 1) + i) * N + x], q);
-    u64 r = mul_shoup(d, pinv[i], pinv[num_q + i], q);
-    const u64* add = comp == 0 ? add0 : add1;
+    u64 d = sub_mod(v[((size_t)b * E + i) * N + x], w[((size_t)b * (level + 1) + i) * N + x], m.q);
+    u64 r = mul_shoup(d, pinv[i], pinv[num_q + i], m.q);
+    const u64* add = comp == 0 ? it.add0 : it.add1;
     if (add) {
-        const u32 xs = g == 1 ? x : galois_gather_index(x, g, log_n);
-        r = add_mod(r, add[(size_t)i * N + xs], q);
+        const u32 xs = it.g == 1 ? x : galois_gather_index(x, it.g, log_n);
+        r = add_mod(r, add[(size_t)i * N + xs], m.q);
     }
-    out[((size_t)comp * (level + 1) + i) * N + x] = r;
+    if (it.mask) r = mulmod_barrett(r, it.mask[(size_t)i * N + x], m);
+    it.out[((size_t)comp * (level + 1) + i) * N + x] = r;
 }
 
-hipError_t launch_moddown_final(const ckks_ctx* c, u32 level, const u64* v, const u64* w, const u64* add0, const u64* add1,
-                                u32 g, u64* out, hipStream_t st) {
-    dim3 grid((c->N + KS_THREADS - 1) / KS_THREADS, level + 1, 2);
-    { ProfScope ps__(c, K_MODDOWN_FINAL, st, 8.0 * c->N * (level + 1.0) * (6.0 + (add0 ? 1.0 : 0.0) + (add1 ? 1.0 : 0.0)), 2.0 * c->N * (level + 1.0)); hipLaunchKernelGGL(moddown_final_kernel, grid, dim3(KS_THREADS), 0, st, v, w, add0, add1, out, c->d_moddown, c->d_mc,
-                       c->log_n, level, c->num_q, c->num_p, c->ext_limbs(level), g); }
+hipError_t launch_moddown_final(const ckks_ctx* c, u32 level, const u64* v, const u64* w, const FinalItem* items, u32 n, hipStream_t st) {
+    FinalBatch B;
+    double extra = 0.0;
+    for (u32 r = 0; r < KS_MAX_BATCH; r++) {
+        if (r < n) {
+            B.it[r] = items[r];
+            extra += (items[r].add0 ? 1.0 : 0.0) + (items[r].add1 ? 1.0 : 0.0) + (items[r].mask ? 1.0 : 0.0);
+        } else {
+            B.it[r] = FinalItem{nullptr, nullptr, nullptr, nullptr, 1, 0};
+        }
+    }
+    dim3 grid((c->N + KS_THREADS - 1) / KS_THREADS, level + 1, 2 * n);
+    ProfScope ps__(c, K_MODDOWN_FINAL, st, 8.0 * c->N * (level + 1.0) * (6.0 * n + extra), 2.0 * c->N * (level + 1.0) * n);
+    hipLaunchKernelGGL(moddown_final_kernel, grid, dim3(KS_THREADS), 0, st, v, w, B, c->d_moddown, c->d_mc, c->log_n, level,
+                       c->num_q, c->num_p, c->ext_limbs(level));
     return hipGetLastError();
 }

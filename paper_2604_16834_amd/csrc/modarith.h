@@ -92,3 +92,44 @@ __host__ __device__ __forceinline__ u64 add_mod(u64 a, u64 b, u64 q) {
 __host__ __device__ __forceinline__ u64 sub_mod(u64 a, u64 b, u64 q) {
     return a >= b ? a - b : a + q - b;
 }
+
+// ---- carry-free accumulation of products of residues below 2^50 ------------------------------
+// Each operand is split into 25-bit halves (l, h) and their sum s; one product costs three
+// 32x32+64 multiply-adds (Karatsuba) into three plain 64-bit sums, so up to 4096 products can be
+// accumulated without a single carry:  sum xl*wl, sum xh*wh, sum (xl+xh)*(wl+wh) < 2^64.
+struct Split50 {
+    u32 l, h, s;
+};
+struct Acc50 {
+    u64 ll, hh, kk;
+};
+#define ACC50_MAX_TERMS 4096u
+
+__host__ __device__ __forceinline__ Split50 split50(u64 v) {
+    Split50 r;
+    r.l = (u32)v & 0x1ffffffu;
+    r.h = (u32)(v >> 25);
+    r.s = r.l + r.h;
+    return r;
+}
+
+__host__ __device__ __forceinline__ void acc50_mad(Acc50& a, const Split50& x, const Split50& w) {
+    a.ll += (u64)x.l * w.l;
+    a.hh += (u64)x.h * w.h;
+    a.kk += (u64)x.s * w.s;
+}
+
+// the accumulated sum as a 128-bit integer: hh*2^50 + (kk - ll - hh)*2^25 + ll
+__host__ __device__ __forceinline__ U128 acc50_value(const Acc50& a) {
+    const u64 mid = a.kk - a.ll - a.hh;
+    U128 r;
+    r.lo = a.ll;
+    r.hi = 0;
+    u64 t = mid << 25;
+    r.lo += t;
+    r.hi += (mid >> 39) + (r.lo < t ? 1ull : 0ull);
+    t = a.hh << 50;
+    r.lo += t;
+    r.hi += (a.hh >> 14) + (r.lo < t ? 1ull : 0ull);
+    return r;
+}

@@ -200,8 +200,83 @@ __global__ __launch_bounds__(PW_THREADS) void weighted_sum_kernel(const u64* __r
         if (o0 + t < c_out) acc[(o0 + t) * ct_stride + off] = barrett_reduce(s[t], m);
 }
 
+// The same sum for moduli below 2^50 (n_terms <= 4096): three multiply-adds per product into plain
+// 64-bit sums, 16 output channels per thread.  The weights are first transposed to
+// wt[limb][term][C_out rounded up to 16] so that the 16 weights of one term are one aligned 128-byte
+// run that the whole wavefront fetches with two wide scalar loads.  Workgroups that read the same xs
+// data (same coefficients, different output tiles) get ids that are 8 apart, so they run at the
+// same time on the same XCD and all but the first are served by that XCD's L2.
+#define WS50_OUT_TILE 16
+__global__ __launch_bounds__(PW_THREADS) void transpose_weights_kernel(const u64* __restrict__ w_res, u64* __restrict__ wt, u32 c_out,
+                                                                       u32 co16, u32 n_terms, u32 L1) {
+    const size_t idx = (size_t)blockIdx.x * PW_THREADS + threadIdx.x;
+    if (idx >= (size_t)L1 * n_terms * co16) return;
+    const u32 o = (u32)(idx % co16);
+    const size_t r = idx / co16;
+    const u32 k = (u32)(r % n_terms), i = (u32)(r / n_terms);
+    wt[idx] = o < c_out ? w_res[((size_t)o * n_terms + k) * L1 + i] : 0;
+}
+
+__global__ __launch_bounds__(PW_THREADS) void weighted_sum50_kernel(const u64* __restrict__ xs, const u64* __restrict__ wt,
+                                                                    u64* __restrict__ acc, const ModConst* __restrict__ mc, u32 N,
+                                                                    u32 level, u32 n_terms, u32 c_out, u32 co16, u32 n_xblocks) {
+    const u32 n_ot = co16 / WS50_OUT_TILE;
+    u32 xb, ot;
+    if ((n_xblocks & 7u) == 0) {  // id = ((xb / 8) * n_ot + ot) * 8 + xb % 8
+        const u32 rest = blockIdx.x >> 3;
+        ot = rest % n_ot;
+        xb = (rest / n_ot) * 8 + (blockIdx.x & 7u);
+    } else {
+        ot = blockIdx.x % n_ot;
+        xb = blockIdx.x / n_ot;
+    }
+    const u32 x = xb * PW_THREADS + threadIdx.x;
+    if (x >= N) return;
+    const u32 L1 = level + 1;
+    const u32 i = blockIdx.y % L1, comp = blockIdx.y / L1;
+    const u32 o0 = ot * WS50_OUT_TILE;
+    const size_t ct_stride = (size_t)2 * L1 * N;
+    const size_t off = ((size_t)comp * L1 + i) * N + x;
+    Acc50 s[WS50_OUT_TILE];
+#pragma unroll
+    for (u32 t = 0; t < WS50_OUT_TILE; t++) s[t] = {0, 0, 0};
+    const u64* wrow = (const u64*)__builtin_assume_aligned(wt + (size_t)i * n_terms * co16 + o0, 128);
+    for (u32 k = 0; k < n_terms; k++) {
+        const Split50 v = split50(xs[k * ct_stride + off]);
+        const u64* wk = (const u64*)__builtin_assume_aligned(wrow + (size_t)k * co16, 128);
+        u64 wv[WS50_OUT_TILE];
+#pragma unroll
+        for (u32 t = 0; t < WS50_OUT_TILE; t++) wv[t] = wk[t];
+#pragma unroll
+        for (u32 t = 0; t < WS50_OUT_TILE; t++) acc50_mad(s[t], v, split50(wv[t]));
+    }
+    const ModConst m = mc[i];
+#pragma unroll
+    for (u32 t = 0; t < WS50_OUT_TILE; t++)
+        if (o0 + t < c_out) acc[(o0 + t) * ct_stride + off] = barrett_reduce(acc50_value(s[t]), m);
+}
+
+size_t weighted_sum_scratch_elems(const ckks_ctx* c, u32 level, u32 n_terms, u32 c_out) {
+    if (!(c->small_q && n_terms <= ACC50_MAX_TERMS)) return 0;
+    const size_t co16 = (c_out + WS50_OUT_TILE - 1) / WS50_OUT_TILE * WS50_OUT_TILE;
+    return (size_t)(level + 1) * n_terms * co16;
+}
+
+// scratch: weighted_sum_scratch_elems() words (may be null when that is 0)
 hipError_t launch_weighted_sum(const ckks_ctx* c, u32 level, const u64* xs, u32 n_terms, const u64* w_res, u32 c_out, u64* acc,
-                               hipStream_t st) {
+                               u64* scratch, hipStream_t st) {
+    if (c->small_q && n_terms <= ACC50_MAX_TERMS) {
+        const u32 co16 = (c_out + WS50_OUT_TILE - 1) / WS50_OUT_TILE * WS50_OUT_TILE, L1 = level + 1;
+        const size_t wt_elems = (size_t)L1 * n_terms * co16;
+        hipLaunchKernelGGL(transpose_weights_kernel, dim3((u32)((wt_elems + PW_THREADS - 1) / PW_THREADS)), dim3(PW_THREADS), 0, st,
+                           w_res, scratch, c_out, co16, n_terms, L1);
+        const u32 n_xblocks = (c->N + PW_THREADS - 1) / PW_THREADS;
+        dim3 grid50(n_xblocks * (co16 / WS50_OUT_TILE), 2 * L1);
+        ProfScope ps__(c, K_WEIGHTED_SUM, st, 16.0 * c->N * (level + 1.0) * ((double)n_terms + c_out), 2.0 * c->N * (level + 1.0) * n_terms * c_out);
+        hipLaunchKernelGGL(weighted_sum50_kernel, grid50, dim3(PW_THREADS), 0, st, xs, scratch, acc, c->d_mc, c->N, level, n_terms, c_out,
+                           co16, n_xblocks);
+        return hipGetLastError();
+    }
     dim3 grid((c->N + PW_THREADS - 1) / PW_THREADS, 2 * (level + 1), (c_out + WS_OUT_TILE - 1) / WS_OUT_TILE);
     { ProfScope ps__(c, K_WEIGHTED_SUM, st, 16.0 * c->N * (level + 1.0) * ((double)n_terms + c_out), 2.0 * c->N * (level + 1.0) * n_terms * c_out); hipLaunchKernelGGL(weighted_sum_kernel, grid, dim3(PW_THREADS), 0, st, xs, w_res, acc, c->d_mc, c->N, level, n_terms, c_out,
                        c->lazy_terms); }

@@ -51,10 +51,10 @@ def test_ntt_single_limb_single_poly():
 
 
 # --------------------------------------------------------------------------------- key switching
-@pytest.fixture(scope="module")
-def ks_setup():
+@pytest.fixture(scope="module", params=[50, 57], ids=["q50", "q57"])
+def ks_setup(request):
     wl = CONFIGS["small_rotations"]          # N = 2^13, 7 limbs in digits of 3,3,1, 3 special primes
-    p = wl.params()
+    p = make_params(wl.log_n, wl.num_q, wl.num_p, wl.dnum, bits=request.param)   # 57-bit primes: general kernels
     orc, ctx = both(p)
     s, s_ntt = orc.gen_secret(11)
     rlk = orc.gen_relin_key(s_ntt, 12)
@@ -133,9 +133,9 @@ def test_ctct_mul_relin_matches_oracle(ks_setup, level):
 
 
 # ----------------------------------------------------------------------------------- convolution
-def conv_case(name, level=None):
+def conv_case(name, level=None, bits=50):
     wl = CONFIGS[name]
-    p = wl.params()
+    p = make_params(wl.log_n, wl.num_q, wl.num_p, wl.dnum, bits=bits)
     orc, ctx = both(p)
     level = p.num_q - 1 if level is None else level
     s, s_ntt = orc.gen_secret(101)
@@ -152,15 +152,17 @@ def conv_case(name, level=None):
     return wl, p, orc, level, s_ntt, img, w, scale, cts, keys, masks, w_int, [hx.to_host(o) for o in outs]
 
 
-@pytest.mark.parametrize("name,level", [("cfg1_single_conv", None), ("cfg1_single_conv_k1", None), ("small_conv", None), ("small_conv", 2)])
-def test_he_conv_matches_oracle_and_float_conv(name, level):
-    wl, p, orc, level, s_ntt, img, w, scale, cts, keys, masks, w_int, outs = conv_case(name, level)
+@pytest.mark.parametrize("name,level,bits", [("cfg1_single_conv", None, 50), ("cfg1_single_conv_k1", None, 50), ("small_conv", None, 50),
+                                             ("small_conv", 2, 50), ("small_conv", None, 56), ("small_conv", None, 36)])
+def test_he_conv_matches_oracle_and_float_conv(name, level, bits):
+    # 56-bit primes take the general 128-bit accumulation kernels, <= 50-bit ones the carry-free split ones
+    wl, p, orc, level, s_ntt, img, w, scale, cts, keys, masks, w_int, outs = conv_case(name, level, bits)
     want = orc.he_conv(cts, level, wl.width, keys, masks, w_int)
     ref = conv2d_reference(img, w)
     for o in range(wl.c_out):
         assert np.array_equal(outs[o], want[o]), f"output channel {o}"
-        if name.endswith("_k1"):
-            continue    # one special prime for 2-limb digits: limb parity only, decryption is noise
+        if name.endswith("_k1") or bits < 50:
+            continue    # one special prime for 2-limb digits / 36-bit primes under a 2^40 scale: limb parity only
         dec = orc.unpack_channel(orc.decrypt(outs[o], level - 1, s_ntt, scale), wl.batch, wl.height, wl.width)
         assert np.abs(dec - ref[:, o]).max() < 1e-4
 
