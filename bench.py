@@ -111,15 +111,14 @@ def main():
     act_out = [hx.empty(2, level - 4, N) for _ in range(wl.c_out)]
     k_act = (3 << 40, -(5 << 40), 7 << 40, -(9 << 40))
     ws_bytes = max(hx.he_conv_workspace_bytes(ctx, wl.c_in, wl.c_out, wl.height, wl.width, wl.batch, level),
-                   hx.ckks_workspace_bytes(ctx, hx.binding.CKKS_OP_POLY_ACT, level - 1))
+                   hx.ckks_workspace_bytes(ctx, hx.binding.CKKS_OP_POLY_ACT, level - 1, wl.c_out))
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
     torch.cuda.synchronize()
     print("[bench] setup %.1f s, workspace %.2f GiB" % (time.perf_counter() - t_setup, ws_bytes / 2**30), file=sys.stderr, flush=True)
 
     def step():
         hx.he_conv_batched(ctx, wl.height, wl.width, wl.batch, level, ins, keys, masks, w_res, wl.c_out, outs=conv_out, ws=ws)
-        for o in range(wl.c_out):
-            hx.he_poly_act_deg7(ctx, conv_out[o], level - 1, k_act, rlk, out=act_out[o], ws=ws)
+        hx.he_poly_act_deg7(ctx, conv_out, level - 1, k_act, rlk, outs=act_out, ws=ws)
 
     for _ in range(args.warmup):
         step()

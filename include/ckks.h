@@ -76,7 +76,7 @@ typedef enum ckks_op {
     CKKS_OP_ROTATE = 1,        /* count = number of rotations in the call */
     CKKS_OP_RESCALE = 2,
     CKKS_OP_CTCT_MUL_RELIN = 3,
-    CKKS_OP_POLY_ACT = 5       /* the convolution has its own query, he_conv_workspace_bytes() */
+    CKKS_OP_POLY_ACT = 5       /* count = number of ciphertexts; the convolution has its own query */
 } ckks_op;
 
 /* Bytes of workspace the given operation needs at `level` (0 on invalid arguments). */
@@ -162,13 +162,18 @@ int he_conv_batched(const ckks_ctx* ctx, const he_conv_desc* desc, const uint64_
                     const ckks_key* const* rot_keys, const uint64_t* d_tap_masks, const uint64_t* d_w_res,
                     uint64_t* const* h_d_out, void* d_ws, size_t ws_bytes, void* stream);
 
-/* Odd degree-7 polynomial activation on one ciphertext with four ciphertext products
- * ("Other Layers"):  x2 = x*x, x3 = x2*x, x4 = x2*x2 (each rescaled once),
+/* Odd degree-7 polynomial activation on a vector of n_ct channel ciphertexts, four ciphertext
+ * products each ("Other Layers": the activation applied independently to every element of the
+ * channel vector):  x2 = x*x, x3 = x2*x, x4 = x2*x2 (each rescaled once),
  *   B = Rescale(k[2]*x + k[3]*x3),  y = Rescale((k[0]*x + k[1]*x3) + x4*B).
  * h_k: four signed integers that fold the polynomial coefficients and the scale ratios (the caller
- * tracks scales).  d_x uint64[2][level+1][N], level >= 4  ->  d_out uint64[2][level-3][N]. */
-int he_poly_act_deg7(const ckks_ctx* ctx, const uint64_t* d_x, uint32_t level, const int64_t* h_k,
-                     const ckks_key* rlk, uint64_t* d_out, void* d_ws, size_t ws_bytes, void* stream);
+ * tracks scales; the same four for every channel).  h_d_x: n_ct device pointers uint64[2][level+1][N],
+ * level >= 4; h_d_out: n_ct device pointers uint64[2][level-3][N].  Channels are processed in
+ * batches that share one pass over the relinearisation key; workspace from
+ * ckks_workspace_bytes(ctx, CKKS_OP_POLY_ACT, level, n_ct). */
+int he_poly_act_deg7(const ckks_ctx* ctx, const uint64_t* const* h_d_x, uint32_t n_ct, uint32_t level,
+                     const int64_t* h_k, const ckks_key* rlk, uint64_t* const* h_d_out, void* d_ws,
+                     size_t ws_bytes, void* stream);
 
 /* Optional per-kernel timing, for benchmarks (not part of the paper's method; callers that measure).
  * Between ckks_prof_begin and ckks_prof_end every launch of a kernel class whose bit is set in

@@ -86,7 +86,7 @@ def _bind(path: str):
     lib.he_conv_workspace_bytes.argtypes = [vp, C.POINTER(_ConvDesc)]
     lib.he_conv_workspace_bytes.restype = sz
     lib.he_conv_batched.argtypes = [vp, C.POINTER(_ConvDesc), C.POINTER(vp), C.POINTER(vp), vp, vp, C.POINTER(vp), vp, sz, vp]
-    lib.he_poly_act_deg7.argtypes = [vp, vp, u32, C.POINTER(C.c_int64), vp, vp, vp, sz, vp]
+    lib.he_poly_act_deg7.argtypes = [vp, C.POINTER(vp), u32, u32, C.POINTER(C.c_int64), vp, C.POINTER(vp), vp, sz, vp]
     lib.ckks_prof_kernel_count.restype = u32
     lib.ckks_prof_kernel_name.argtypes = [u32]
     lib.ckks_prof_kernel_name.restype = C.c_char_p
@@ -327,16 +327,27 @@ def he_conv_batched(ctx: Context, height: int, width: int, batch: int, level: in
     return outs
 
 
-def he_poly_act_deg7(ctx: Context, x: torch.Tensor, level: int, k: Sequence[int], rlk: Key, out: Optional[torch.Tensor] = None,
-                     ws: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
-    if x.numel() != 2 * (level + 1) * ctx.N or len(k) != 4:
-        raise ValueError("x must be [2][level+1][N] and k four integers")
-    if out is None:
-        out = empty(2, max(level - 3, 1), ctx.N)
-    ws = _ws(ctx, ws, ckks_workspace_bytes(ctx, CKKS_OP_POLY_ACT, level))
+def he_poly_act_deg7(ctx: Context, xs: Sequence[torch.Tensor], level: int, k: Sequence[int], rlk: Key,
+                     outs: Optional[List[torch.Tensor]] = None, ws: Optional[torch.Tensor] = None, stream=None) -> List[torch.Tensor]:
+    """xs: channel ciphertexts [2][level+1][N]; returns one [2][level-3][N] per channel."""
+    n = len(xs)
+    if n == 0 or len(k) != 4:
+        raise ValueError("need at least one ciphertext and four integers k")
+    for x in xs:
+        if x.numel() != 2 * (level + 1) * ctx.N:
+            raise ValueError("each x must be [2][level+1][N]")
+    if outs is None:
+        outs = [empty(2, max(level - 3, 1), ctx.N) for _ in range(n)]
+    for o in outs:
+        if o.numel() != 2 * (level - 3) * ctx.N:
+            raise ValueError("each output must be [2][level-3][N]")
+    ws = _ws(ctx, ws, ckks_workspace_bytes(ctx, CKKS_OP_POLY_ACT, level, n))
     ka = (C.c_int64 * 4)(*[int(v) for v in k])
-    ctx._check(_lib.he_poly_act_deg7(ctx.handle, _ptr(x), level, ka, rlk.handle if rlk else None, _ptr(out), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)))
-    return out
+    xa = _ptr_array([_ptr(x) for x in xs])
+    oa = _ptr_array([_ptr(o) for o in outs])
+    ctx._check(_lib.he_poly_act_deg7(ctx.handle, xa, n, level, ka, rlk.handle if rlk else None, oa, _ptr(ws),
+                                     ws.numel() * ws.element_size(), _stream(stream)))
+    return outs
 
 
 def ckks_prof_kernel_names() -> List[str]:

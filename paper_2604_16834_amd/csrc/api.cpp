@@ -1,5 +1,10 @@
 // The C boundary: argument checks, workspace carving and the order of kernel launches of every
 // exported operation.  No arithmetic happens on the host; no call here allocates or synchronises.
+//
+// Work is batched wherever operands are independent: the channel ciphertexts of a layer share their
+// rotation and relinearisation keys, so up to CT_BATCH of them go through every kernel of a key
+// switch together (the key streams from HBM once per batch, NTT launches are large enough to fill
+// the chip); the rotations of one ciphertext share its extended digits (hoisting).
 #include <cstdio>
 #include <new>
 
@@ -34,6 +39,7 @@ struct Arena {
         return r;
     }
     bool ok() const { return used <= cap; }
+    Arena rest() const { return ok() ? Arena(base + used, cap - used) : Arena(nullptr, 0); }
 };
 size_t blk(size_t elems) { return (elems * sizeof(u64) + 255) & ~(size_t)255; }
 
@@ -47,36 +53,54 @@ PolyList range_list(u32 first_pos, u32 count, u32 first_mod) {
     return pl;
 }
 
-// ---- workspace sizes ---------------------------------------------------------------------------
-// rb = how many key switches share one pass of the ModDown kernels (1..KS_MAX_BATCH)
-size_t ws_keyswitch(const ckks_ctx* c, u32 level, u32 rb = 1) {
-    const size_t N = c->N, L1 = level + 1, E = c->ext_limbs(level), beta = c->live_digits(level);
-    return blk(L1 * N) + blk(beta * E * N) + blk(rb * 2 * E * N) + blk(rb * 2 * L1 * N);
+PtrList8 ptr_list(const u64* const* p, u32 n) {
+    PtrList8 l;
+    for (u32 b = 0; b < KS_MAX_BATCH; b++) l.p[b] = b < n ? p[b] : nullptr;
+    return l;
 }
-size_t ws_rescale(const ckks_ctx* c, u32 level) { return blk(2 * (size_t)c->N) + blk(2 * (size_t)level * c->N); }
-size_t ws_ctct(const ckks_ctx* c, u32 level) { return 3 * blk((size_t)(level + 1) * c->N) + ws_keyswitch(c, level); }
+OutList8 out_list(u64* const* p, u32 n) {
+    OutList8 l;
+    for (u32 b = 0; b < KS_MAX_BATCH; b++) l.p[b] = b < n ? p[b] : nullptr;
+    return l;
+}
 
-struct KsBuffers {
+bool level_ok(const ckks_ctx* c, u32 level) { return level < c->num_q; }
+
+// ---- key-switch workspace: n_dig polynomials being decomposed, n_v key switches in flight ----------
+struct KsWs {
     u64 *y, *digits, *v, *w;
+    size_t y_b, dig_b, v_b, w_b;  // per-item strides in elements
 };
-bool carve_ks(const ckks_ctx* c, u32 level, Arena& ar, KsBuffers& b, u32 rb = 1) {
+size_t ws_ks(const ckks_ctx* c, u32 level, u32 n_dig, u32 n_v) {
     const size_t N = c->N, L1 = level + 1, E = c->ext_limbs(level), beta = c->live_digits(level);
-    b.y = ar.take(L1 * N);
-    b.digits = ar.take(beta * E * N);
-    b.v = ar.take(rb * 2 * E * N);
-    b.w = ar.take(rb * 2 * L1 * N);
+    return blk(n_dig * L1 * N) + blk(n_dig * beta * E * N) + blk(n_v * 2 * E * N) + blk(n_v * 2 * L1 * N);
+}
+bool carve_ks(const ckks_ctx* c, u32 level, u32 n_dig, u32 n_v, Arena& ar, KsWs& b) {
+    const size_t N = c->N, L1 = level + 1, E = c->ext_limbs(level), beta = c->live_digits(level);
+    b.y_b = L1 * N;
+    b.dig_b = beta * E * N;
+    b.v_b = 2 * E * N;
+    b.w_b = 2 * L1 * N;
+    b.y = ar.take(n_dig * b.y_b);
+    b.digits = ar.take(n_dig * b.dig_b);
+    b.v = ar.take(n_v * b.v_b);
+    b.w = ar.take(n_v * b.w_b);
     return ar.ok();
 }
+size_t ws_rescale(const ckks_ctx* c, u32 level, u32 n) { return blk(2 * (size_t)n * c->N) + blk(2 * (size_t)n * level * c->N); }
+size_t ws_ctct(const ckks_ctx* c, u32 level, u32 n) { return 3 * blk((size_t)n * (level + 1) * c->N) + ws_ks(c, level, n, n); }
 
-// Decompose + ModUp of one polynomial d_c [level+1][N] (NTT form) into b.digits [beta][E][N] (NTT form).
-int run_modup(const ckks_ctx* c, u32 level, const u64* d_c, const KsBuffers& b, hipStream_t st) {
+// Decompose + ModUp of n <= CT_BATCH polynomials srcs[b] ([level+1][N], NTT form) into
+// ws.digits + b*ws.dig_b ([beta][E][N], NTT form).
+int run_modup(const ckks_ctx* c, u32 level, const u64* const* srcs, u32 n, const KsWs& ws, hipStream_t st) {
     const u32 N = c->N, L1 = level + 1, E = c->ext_limbs(level), beta = c->live_digits(level);
-    // all live limbs to coefficient form at once
-    HIP_TRY(launch_ntt(c, true, d_c, L1, b.y, L1, range_list(0, L1, 0), 1, st));
+    // all live limbs of every polynomial to coefficient form at once
+    HIP_TRY(launch_ntt(c, true, nullptr, 0, ws.y, L1, range_list(0, L1, 0), n, st, srcs));
+    const PtrList8 cl = ptr_list(srcs, n);
     for (u32 j = 0; j < beta; j++) {
         const u32 lo = c->digit_lo(j), hi = c->digit_hi(j, level);
-        u64* digit = b.digits + (size_t)j * E * N;
-        HIP_TRY(launch_modup_conv(c, level, j, b.y + (size_t)lo * N, d_c, digit, st));
+        u64* digit = ws.digits + (size_t)j * E * N;
+        HIP_TRY(launch_modup_conv(c, level, j, ws.y + (size_t)lo * N, ws.y_b, cl, digit, ws.dig_b, n, st));
         PolyList pl;
         pl.n = 0;
         for (u32 e = 0; e < E; e++) {
@@ -87,58 +111,69 @@ int run_modup(const ckks_ctx* c, u32 level, const u64* d_c, const KsBuffers& b, 
             pl.n++;
         }
         for (u32 a = pl.n; a < CKKS_MAX_MODULI; a++) pl.spos[a] = pl.dpos[a] = pl.mod[a] = 0;
-        HIP_TRY(launch_ntt(c, false, digit, E, digit, E, pl, 1, st));
+        HIP_TRY(launch_ntt(c, false, digit, (size_t)beta * E, digit, (size_t)beta * E, pl, n, st));
     }
     return CKKS_OK;
 }
 
-// n <= KS_MAX_BATCH key switches of the same extended digits: inner product with each key (digits read
-// through sigma_g of the item), then one pass of every ModDown kernel over the whole batch.  items[r]
-// says what is added to / multiplied into the r-th result and where it goes ([2][level+1][N]).
-int run_inner_moddown(const ckks_ctx* c, u32 level, const KsBuffers& b, u32 n, const u64* const* d_keys, const FinalItem* items,
-                      hipStream_t st) {
+// ModDown of the n inner products sitting in ws.v: one pass of each kernel over the whole batch.
+// items[r] says what is added to / multiplied into the r-th result and where it goes ([2][level+1][N]).
+int run_moddown(const ckks_ctx* c, u32 level, const KsWs& ws, u32 n, const FinalItem* items, hipStream_t st) {
     const u32 L1 = level + 1, E = c->ext_limbs(level), k = c->num_p;
-    const size_t N = c->N;
-    for (u32 r = 0; r < n; r++) HIP_TRY(launch_key_inner(c, level, b.digits, d_keys[r], items[r].g, b.v + (size_t)r * 2 * E * N, st));
-    // P-part of every component to coefficient form, in place
-    HIP_TRY(launch_ntt(c, true, b.v, E, b.v, E, range_list(L1, k, c->num_q), 2 * n, st));
-    HIP_TRY(launch_moddown_conv(c, level, b.v, b.w, 2 * n, st));
-    HIP_TRY(launch_ntt(c, false, b.w, L1, b.w, L1, range_list(0, L1, 0), 2 * n, st));
-    HIP_TRY(launch_moddown_final(c, level, b.v, b.w, items, n, st));
+    HIP_TRY(launch_ntt(c, true, ws.v, E, ws.v, E, range_list(L1, k, c->num_q), 2 * n, st));  // P-part -> coefficients
+    HIP_TRY(launch_moddown_conv(c, level, ws.v, ws.w, 2 * n, st));
+    HIP_TRY(launch_ntt(c, false, ws.w, L1, ws.w, L1, range_list(0, L1, 0), 2 * n, st));
+    HIP_TRY(launch_moddown_final(c, level, ws.v, ws.w, items, n, st));
     return CKKS_OK;
 }
 
-int run_rescale(const ckks_ctx* c, u32 level, const u64* ct, size_t ct_cstride, u64* out, Arena& ar, hipStream_t st) {
+// n <= CT_BATCH ciphertexts cts[b] (component stride ct_cstride) rescaled from `level` into outs[b]
+int run_rescale(const ckks_ctx* c, u32 level, const u64* const* cts, size_t ct_cstride, u64* const* outs, u32 n, Arena ar,
+                hipStream_t st) {
     const size_t N = c->N;
-    u64* r = ar.take(2 * N);
-    u64* w = ar.take(2 * (size_t)level * N);
+    u64* r = ar.take(2 * (size_t)n * N);
+    u64* w = ar.take(2 * (size_t)n * level * N);
     if (!ar.ok()) return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for rescale");
-    // dropped limb of both components -> coefficient form
-    PolyList pl = range_list(0, 1, level);
-    HIP_TRY(launch_ntt(c, true, ct + (size_t)level * N, ct_cstride / N, r, 1, pl, 2, st));
-    HIP_TRY(launch_rescale_conv(c, level, r, w, st));
-    HIP_TRY(launch_ntt(c, false, w, level, w, level, range_list(0, level, 0), 2, st));
-    HIP_TRY(launch_rescale_final(c, level, ct, ct_cstride, w, out, st));
+    const u64* last[KS_MAX_BATCH];  // the dropped limb of every component
+    for (u32 b = 0; b < n; b++) {
+        last[2 * b] = cts[b] + (size_t)level * N;
+        last[2 * b + 1] = cts[b] + ct_cstride + (size_t)level * N;
+    }
+    HIP_TRY(launch_ntt(c, true, nullptr, 0, r, 1, range_list(0, 1, level), 2 * n, st, last));
+    HIP_TRY(launch_rescale_conv(c, level, r, w, 2 * n, st));
+    HIP_TRY(launch_ntt(c, false, w, level, w, level, range_list(0, level, 0), 2 * n, st));
+    HIP_TRY(launch_rescale_final(c, level, ptr_list(cts, n), ct_cstride, w, out_list(outs, n), n, st));
     return CKKS_OK;
 }
 
-// (a*b relinearised) with operands possibly living at a higher level (component strides given)
-int run_ctct(const ckks_ctx* c, u32 level, const u64* a, size_t a_cstride, const u64* b, size_t b_cstride, const u64* d_rlk,
-             u64* out, Arena& ar, hipStream_t st) {
+// n <= CT_BATCH products a[b]*b[b] with relinearisation (operands possibly at a higher level:
+// component strides given); outs[b] = [2][level+1][N]
+int run_ctct(const ckks_ctx* c, u32 level, const u64* const* a, size_t a_cstride, const u64* const* b, size_t b_cstride,
+             const u64* d_rlk, u64* const* outs, u32 n, Arena ar, hipStream_t st) {
     const size_t N = c->N, L1 = level + 1;
-    u64* d0 = ar.take(L1 * N);
-    u64* d1 = ar.take(L1 * N);
-    u64* d2 = ar.take(L1 * N);
-    KsBuffers kb;
-    if (!carve_ks(c, level, ar, kb)) return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for ct-ct multiply");
-    HIP_TRY(launch_tensor(c, level, a, a_cstride, b, b_cstride, d0, d1, d2, st));
-    int rc = run_modup(c, level, d2, kb, st);
+    u64* d0 = ar.take(n * L1 * N);
+    u64* d1 = ar.take(n * L1 * N);
+    u64* d2 = ar.take(n * L1 * N);
+    KsWs ws;
+    if (!carve_ks(c, level, n, n, ar, ws)) return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for ct-ct multiply");
+    HIP_TRY(launch_tensor(c, level, ptr_list(a, n), a_cstride, ptr_list(b, n), b_cstride, d0, d1, d2, n, st));
+    const u64* d2s[CT_BATCH];
+    FinalItem items[CT_BATCH];
+    for (u32 i = 0; i < n; i++) {
+        d2s[i] = d2 + i * L1 * N;
+        items[i] = FinalItem{d0 + i * L1 * N, d1 + i * L1 * N, nullptr, outs[i], 1, 0};
+    }
+    int rc = run_modup(c, level, d2s, n, ws, st);
     if (rc) return rc;
-    const FinalItem item = {d0, d1, nullptr, out, 1, 0};
-    return run_inner_moddown(c, level, kb, 1, &d_rlk, &item, st);
+    HIP_TRY(launch_key_inner_multi(c, level, ws.digits, ws.dig_b, d_rlk, 1, ws.v, ws.v_b, n, st));
+    return run_moddown(c, level, ws, n, items, st);
 }
 
-bool level_ok(const ckks_ctx* c, u32 level) { return level < c->num_q; }
+size_t ws_poly_act(const ckks_ctx* c, u32 level, u32 n) {
+    const size_t N = c->N;
+    return blk(2 * (size_t)n * level * N) + 2 * blk(2 * (size_t)n * (level - 1) * N) + blk(2 * (size_t)n * (level - 2) * N) +
+           blk(2 * (size_t)n * (level + 1) * N) + ws_ctct(c, level, n) + ws_rescale(c, level, n);
+}
 
 }  // namespace
 
@@ -147,31 +182,22 @@ extern "C" {
 size_t ckks_workspace_bytes(const ckks_ctx* c, int op, uint32_t level, uint32_t count) {
     if (!c || !level_ok(c, level)) return 0;
     const size_t N = c->N, L1 = level + 1;
+    const u32 nb = count < 1 ? 1 : (count > CT_BATCH ? CT_BATCH : count);
     switch (op) {
-        case CKKS_OP_KEYSWITCH: return c->dnum ? ws_keyswitch(c, level) : 0;
-        case CKKS_OP_ROTATE: {
-            const u32 rb = count < 1 ? 1 : (count > KS_MAX_BATCH ? KS_MAX_BATCH : count);
-            return c->dnum ? ws_keyswitch(c, level, rb) + blk(L1 * N) : 0;
-        }
-        case CKKS_OP_RESCALE: return level >= 1 ? ws_rescale(c, level) : 0;
-        case CKKS_OP_CTCT_MUL_RELIN: return c->dnum ? ws_ctct(c, level) : 0;
-        case CKKS_OP_POLY_ACT: {
-            if (!c->dnum || level < 4) return 0;
-            // x2 [level], x3, x4 [level-1], B [level-2], product/pre-rescale scratch [level+1], plus one
-            // ct-ct multiply and one rescale at the top level
-            size_t s = blk(2 * (size_t)level * N) + 2 * blk(2 * (size_t)(level - 1) * N) + blk(2 * (size_t)(level - 2) * N) +
-                       blk(2 * L1 * N);
-            return s + ws_ctct(c, level) + ws_rescale(c, level);
-        }
-        default: (void)count; return 0;
+        case CKKS_OP_KEYSWITCH: return c->dnum ? ws_ks(c, level, 1, 1) : 0;
+        case CKKS_OP_ROTATE: return c->dnum ? ws_ks(c, level, 1, nb) + blk(L1 * N) : 0;
+        case CKKS_OP_RESCALE: return level >= 1 ? ws_rescale(c, level, 1) : 0;
+        case CKKS_OP_CTCT_MUL_RELIN: return c->dnum ? ws_ctct(c, level, 1) : 0;
+        case CKKS_OP_POLY_ACT: return (c->dnum && level >= 4) ? ws_poly_act(c, level, nb) : 0;
+        default: return 0;
     }
 }
 
 size_t he_conv_workspace_bytes(const ckks_ctx* c, const he_conv_desc* d) {
     if (!c || !d || !c->dnum || !level_ok(c, d->level) || d->level < 1) return 0;
     const size_t N = c->N, L1 = d->level + 1;
-    return ws_keyswitch(c, d->level, KS_MAX_BATCH) + blk((size_t)d->c_in * 9 * 2 * L1 * N) + blk((size_t)d->c_out * 2 * L1 * N) +
-           blk(weighted_sum_scratch_elems(c, d->level, d->c_in * 9, d->c_out)) + ws_rescale(c, d->level);
+    return ws_ks(c, d->level, CT_BATCH, CT_BATCH) + blk((size_t)d->c_in * 9 * 2 * L1 * N) + blk((size_t)d->c_out * 2 * L1 * N) +
+           blk(weighted_sum_scratch_elems(c, d->level, d->c_in * 9, d->c_out)) + ws_rescale(c, d->level, CT_BATCH);
 }
 
 uint32_t ckks_galois_element(const ckks_ctx* c, int32_t offset) {
@@ -239,13 +265,15 @@ int ckks_keyswitch(const ckks_ctx* c, const uint64_t* d_c, uint32_t level, const
     if (!c->dnum) return set_err(c, CKKS_ERR_UNSUPPORTED_PARAMS, "context has no key-switching digits");
     if (!level_ok(c, level)) return set_err(c, CKKS_ERR_LEVEL_MISMATCH, "level out of range");
     Arena ar(d_ws, ws_bytes);
-    KsBuffers b;
-    if (!carve_ks(c, level, ar, b)) return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for key switch");
+    KsWs ws;
+    if (!carve_ks(c, level, 1, 1, ar, ws)) return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for key switch");
     hipStream_t st = (hipStream_t)stream;
-    int rc = run_modup(c, level, (const u64*)d_c, b, st);
+    const u64* src = (const u64*)d_c;
+    int rc = run_modup(c, level, &src, 1, ws, st);
     if (rc) return rc;
+    HIP_TRY(launch_key_inner(c, level, ws.digits, key->d_key, 1, ws.v, st));
     const FinalItem item = {nullptr, nullptr, nullptr, (u64*)d_out, 1, 0};
-    return run_inner_moddown(c, level, b, 1, &key->d_key, &item, st);
+    return run_moddown(c, level, ws, 1, &item, st);
 }
 
 int ckks_rotate_hoisted(const ckks_ctx* c, const uint64_t* d_ct, uint32_t level, const int32_t* h_offsets, uint32_t n_rot,
@@ -257,24 +285,22 @@ int ckks_rotate_hoisted(const ckks_ctx* c, const uint64_t* d_ct, uint32_t level,
     if (!level_ok(c, level)) return set_err(c, CKKS_ERR_LEVEL_MISMATCH, "level out of range");
     const size_t N = c->N, L1 = level + 1;
     // validate everything before the first launch
-    bool any = false;
+    u32 n_keyed = 0;
     for (u32 t = 0; t < n_rot; t++) {
         if (!h_d_outs[t]) return set_err(c, CKKS_ERR_INVALID_ARG, "null output pointer");
         const u32 g = ckks_galois_element(c, h_offsets[t]);
         if (g == 1) continue;
-        any = true;
+        n_keyed++;
         if (!keys || !keys[t]) return set_err(c, CKKS_ERR_NO_KEY, "rotation key missing");
         if (keys[t]->galois_elt != g) return set_err(c, CKKS_ERR_NO_KEY, "rotation key was made for another offset");
     }
-    // hoisted rotations go through the ModDown kernels in batches of up to KS_MAX_BATCH
-    u32 n_keyed = 0;
-    for (u32 t = 0; t < n_rot; t++) n_keyed += ckks_galois_element(c, h_offsets[t]) != 1;
-    const u32 rb = hoisted ? (n_keyed < KS_MAX_BATCH ? (n_keyed ? n_keyed : 1) : KS_MAX_BATCH) : 1;
+    // hoisted rotations go through the ModDown kernels in batches of up to CT_BATCH
+    const u32 rb = hoisted ? (n_keyed < CT_BATCH ? (n_keyed ? n_keyed : 1) : CT_BATCH) : 1;
     Arena ar(d_ws, ws_bytes);
-    KsBuffers b = {nullptr, nullptr, nullptr, nullptr};
+    KsWs ws = {};
     u64* pc1 = nullptr;
-    if (any) {
-        if (!carve_ks(c, level, ar, b, rb)) return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for rotation");
+    if (n_keyed) {
+        if (!carve_ks(c, level, 1, rb, ar, ws)) return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for rotation");
         if (!hoisted) {
             pc1 = ar.take(L1 * N);
             if (!ar.ok()) return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for rotation");
@@ -284,12 +310,11 @@ int ckks_rotate_hoisted(const ckks_ctx* c, const uint64_t* d_ct, uint32_t level,
     const u64* ct = (const u64*)d_ct;
     const u64* c0 = ct;
     const u64* c1 = ct + L1 * N;
-    if (any && hoisted) {
-        int rc = run_modup(c, level, c1, b, st);
+    if (n_keyed && hoisted) {
+        int rc = run_modup(c, level, &c1, 1, ws, st);
         if (rc) return rc;
     }
-    FinalItem items[KS_MAX_BATCH];
-    const u64* bkeys[KS_MAX_BATCH];
+    FinalItem items[CT_BATCH];
     u32 nb = 0;
     for (u32 t = 0; t < n_rot; t++) {
         const u32 g = ckks_galois_element(c, h_offsets[t]);
@@ -299,29 +324,27 @@ int ckks_rotate_hoisted(const ckks_ctx* c, const uint64_t* d_ct, uint32_t level,
             continue;
         }
         if (hoisted) {
+            // same digits, one key per rotation; the digits are read through sigma_g
+            HIP_TRY(launch_key_inner(c, level, ws.digits, keys[t]->d_key, g, ws.v + nb * ws.v_b, st));
             items[nb] = FinalItem{c0, nullptr, nullptr, out, g, 0};
-            bkeys[nb] = keys[t]->d_key;
             if (++nb == rb) {
-                int rc = run_inner_moddown(c, level, b, nb, bkeys, items, st);
+                int rc = run_moddown(c, level, ws, nb, items, st);
                 if (rc) return rc;
                 nb = 0;
             }
         } else {
             HIP_TRY(launch_automorph(c, (u32)L1, c1, g, pc1, st));
-            int rc = run_modup(c, level, pc1, b, st);
+            const u64* src = pc1;
+            int rc = run_modup(c, level, &src, 1, ws, st);
             if (rc) return rc;
             // the digits already belong to sigma_g(c1): no gather in the inner product, only on c0
-            const u32 E = c->ext_limbs(level), k = c->num_p;
-            HIP_TRY(launch_key_inner(c, level, b.digits, keys[t]->d_key, 1, b.v, st));
-            HIP_TRY(launch_ntt(c, true, b.v, E, b.v, E, range_list((u32)L1, k, c->num_q), 2, st));
-            HIP_TRY(launch_moddown_conv(c, level, b.v, b.w, 2, st));
-            HIP_TRY(launch_ntt(c, false, b.w, L1, b.w, L1, range_list(0, (u32)L1, 0), 2, st));
+            HIP_TRY(launch_key_inner(c, level, ws.digits, keys[t]->d_key, 1, ws.v, st));
             const FinalItem item = {c0, nullptr, nullptr, out, g, 0};
-            HIP_TRY(launch_moddown_final(c, level, b.v, b.w, &item, 1, st));
+            if ((rc = run_moddown(c, level, ws, 1, &item, st))) return rc;
         }
     }
     if (nb) {
-        int rc = run_inner_moddown(c, level, b, nb, bkeys, items, st);
+        int rc = run_moddown(c, level, ws, nb, items, st);
         if (rc) return rc;
     }
     return CKKS_OK;
@@ -343,8 +366,9 @@ int ckks_rescale(const ckks_ctx* c, const uint64_t* d_ct, uint32_t level, uint64
     if (!c) return CKKS_ERR_INVALID_ARG;
     if (!d_ct || !d_out) return set_err(c, CKKS_ERR_INVALID_ARG, "null pointer");
     if (!level_ok(c, level) || level < 1) return set_err(c, CKKS_ERR_LEVEL_MISMATCH, "rescale needs 1 <= level < num_q");
-    Arena ar(d_ws, ws_bytes);
-    return run_rescale(c, level, (const u64*)d_ct, (size_t)(level + 1) * c->N, (u64*)d_out, ar, (hipStream_t)stream);
+    const u64* ct = (const u64*)d_ct;
+    u64* out = (u64*)d_out;
+    return run_rescale(c, level, &ct, (size_t)(level + 1) * c->N, &out, 1, Arena(d_ws, ws_bytes), (hipStream_t)stream);
 }
 
 int ckks_ctct_mul_relin(const ckks_ctx* c, const uint64_t* d_a, const uint64_t* d_b, uint32_t level, const ckks_key* rlk,
@@ -355,9 +379,11 @@ int ckks_ctct_mul_relin(const ckks_ctx* c, const uint64_t* d_a, const uint64_t* 
     if (!rlk) return set_err(c, CKKS_ERR_NO_KEY, "no relinearisation key");
     if (rlk->galois_elt != 0) return set_err(c, CKKS_ERR_NO_KEY, "key is a rotation key, not the relinearisation key");
     if (!level_ok(c, level)) return set_err(c, CKKS_ERR_LEVEL_MISMATCH, "level out of range");
-    Arena ar(d_ws, ws_bytes);
     const size_t cs = (size_t)(level + 1) * c->N;
-    return run_ctct(c, level, (const u64*)d_a, cs, (const u64*)d_b, cs, rlk->d_key, (u64*)d_out, ar, (hipStream_t)stream);
+    const u64* a = (const u64*)d_a;
+    const u64* b = (const u64*)d_b;
+    u64* out = (u64*)d_out;
+    return run_ctct(c, level, &a, cs, &b, cs, rlk->d_key, &out, 1, Arena(d_ws, ws_bytes), (hipStream_t)stream);
 }
 
 int he_conv_batched(const ckks_ctx* c, const he_conv_desc* d, const uint64_t* const* h_d_in, const ckks_key* const* rot_keys,
@@ -372,14 +398,12 @@ int he_conv_batched(const ckks_ctx* c, const he_conv_desc* d, const uint64_t* co
     if ((u64)d->height * d->width * d->batch > c->N / 2) return set_err(c, CKKS_ERR_INVALID_ARG, "H*W*batch exceeds the N/2 slots");
     const u32 level = d->level;
     const size_t N = c->N, L1 = level + 1, ct_elems = 2 * L1 * N;
-    int32_t offs[9];
     u32 gs[9];
     {
         u32 t = 0;
         for (int dy = -1; dy <= 1; dy++)
             for (int dx = -1; dx <= 1; dx++, t++) {
-                offs[t] = dy * (int32_t)d->width + dx;
-                gs[t] = ckks_galois_element(c, offs[t]);
+                gs[t] = ckks_galois_element(c, dy * (int32_t)d->width + dx);
                 if (gs[t] == 1) continue;
                 if (!rot_keys[t]) return set_err(c, CKKS_ERR_NO_KEY, "rotation key missing for a tap");
                 if (rot_keys[t]->galois_elt != gs[t]) return set_err(c, CKKS_ERR_NO_KEY, "rotation key does not match its tap offset");
@@ -389,46 +413,129 @@ int he_conv_batched(const ckks_ctx* c, const he_conv_desc* d, const uint64_t* co
     for (u32 o = 0; o < d->c_out; o++) if (!h_d_out[o]) return set_err(c, CKKS_ERR_INVALID_ARG, "null output ciphertext");
 
     Arena ar(d_ws, ws_bytes);
-    KsBuffers b;
-    bool ok = carve_ks(c, level, ar, b, KS_MAX_BATCH);
+    KsWs ws;
+    bool ok = carve_ks(c, level, CT_BATCH, CT_BATCH, ar, ws);
     u64* xs = ar.take((size_t)d->c_in * 9 * ct_elems);
     u64* acc = ar.take((size_t)d->c_out * ct_elems);
     u64* wscratch = ar.take(weighted_sum_scratch_elems(c, level, d->c_in * 9, d->c_out));
-    if (!ok || !ar.ok() || ar.used + ws_rescale(c, level) > ar.cap)
+    if (!ok || !ar.ok() || ar.used + ws_rescale(c, level, CT_BATCH) > ar.cap)
         return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for the convolution");
     hipStream_t st = (hipStream_t)stream;
 
-    // input alignment: nine aligned copies of every input channel, each times its tap mask; the eight
-    // rotations of a channel share the decomposition and go through the ModDown kernels as one batch
-    for (u32 ci = 0; ci < d->c_in; ci++) {
-        const u64* ct = (const u64*)h_d_in[ci];
-        int rc = run_modup(c, level, ct + L1 * N, b, st);
+    // input alignment: nine aligned copies of every input channel, each times its tap mask.  Channels
+    // go in batches: one shared pass of the decomposition kernels, then per tap one inner product that
+    // streams the tap's key once for the whole batch and one batched ModDown.
+    for (u32 c0 = 0; c0 < d->c_in; c0 += CT_BATCH) {
+        const u32 n = d->c_in - c0 < CT_BATCH ? d->c_in - c0 : CT_BATCH;
+        const u64* c1s[CT_BATCH];
+        for (u32 b = 0; b < n; b++) c1s[b] = (const u64*)h_d_in[c0 + b] + L1 * N;
+        int rc = run_modup(c, level, c1s, n, ws, st);
         if (rc) return rc;
-        FinalItem items[KS_MAX_BATCH];
-        const u64* bkeys[KS_MAX_BATCH];
-        u32 nb = 0;
         for (u32 t = 0; t < 9; t++) {
             const u64* mask = (const u64*)d_tap_masks + (size_t)t * L1 * N;
-            u64* x = xs + ((size_t)ci * 9 + t) * ct_elems;
             if (gs[t] == 1) {
-                HIP_TRY(launch_mask_mul(c, level, mask, ct, x, st));
+                for (u32 b = 0; b < n; b++)
+                    HIP_TRY(launch_mask_mul(c, level, mask, (const u64*)h_d_in[c0 + b], xs + ((size_t)(c0 + b) * 9 + t) * ct_elems, st));
                 continue;
             }
-            items[nb] = FinalItem{ct, nullptr, mask, x, gs[t], 0};
-            bkeys[nb] = rot_keys[t]->d_key;
-            if (++nb == KS_MAX_BATCH) {
-                if ((rc = run_inner_moddown(c, level, b, nb, bkeys, items, st))) return rc;
-                nb = 0;
-            }
+            HIP_TRY(launch_key_inner_multi(c, level, ws.digits, ws.dig_b, rot_keys[t]->d_key, gs[t], ws.v, ws.v_b, n, st));
+            FinalItem items[CT_BATCH];
+            for (u32 b = 0; b < n; b++)
+                items[b] = FinalItem{(const u64*)h_d_in[c0 + b], nullptr, mask, xs + ((size_t)(c0 + b) * 9 + t) * ct_elems, gs[t], 0};
+            if ((rc = run_moddown(c, level, ws, n, items, st))) return rc;
         }
-        if (nb && (rc = run_inner_moddown(c, level, b, nb, bkeys, items, st))) return rc;
     }
     // convolution evaluation: integer-weighted sum over (input channel, tap) for every output channel
     HIP_TRY(launch_weighted_sum(c, level, xs, d->c_in * 9, (const u64*)d_w_res, d->c_out, acc, wscratch, st));
-    for (u32 o = 0; o < d->c_out; o++) {
-        Arena tmp(ar.base + ar.used, ar.cap - ar.used);
-        int rc = run_rescale(c, level, acc + (size_t)o * ct_elems, L1 * N, (u64*)h_d_out[o], tmp, st);
+    for (u32 o0 = 0; o0 < d->c_out; o0 += CT_BATCH) {
+        const u32 n = d->c_out - o0 < CT_BATCH ? d->c_out - o0 : CT_BATCH;
+        const u64* ins[CT_BATCH];
+        u64* outs[CT_BATCH];
+        for (u32 b = 0; b < n; b++) {
+            ins[b] = acc + (size_t)(o0 + b) * ct_elems;
+            outs[b] = (u64*)h_d_out[o0 + b];
+        }
+        int rc = run_rescale(c, level, ins, L1 * N, outs, n, ar.rest(), st);
         if (rc) return rc;
+    }
+    return CKKS_OK;
+}
+
+int he_poly_act_deg7(const ckks_ctx* c, const uint64_t* const* h_d_x, uint32_t n_ct, uint32_t level, const int64_t* h_k,
+                     const ckks_key* rlk, uint64_t* const* h_d_out, void* d_ws, size_t ws_bytes, void* stream) {
+    if (!c) return CKKS_ERR_INVALID_ARG;
+    if (!h_d_x || !h_k || !h_d_out || n_ct == 0) return set_err(c, CKKS_ERR_INVALID_ARG, "null pointer or no ciphertexts");
+    if (!c->dnum) return set_err(c, CKKS_ERR_UNSUPPORTED_PARAMS, "context has no key-switching digits");
+    if (!rlk) return set_err(c, CKKS_ERR_NO_KEY, "no relinearisation key");
+    if (rlk->galois_elt != 0) return set_err(c, CKKS_ERR_NO_KEY, "key is a rotation key, not the relinearisation key");
+    if (!level_ok(c, level) || level < 4) return set_err(c, CKKS_ERR_LEVEL_MISMATCH, "activation needs 4 <= level < num_q");
+    for (u32 i = 0; i < n_ct; i++)
+        if (!h_d_x[i] || !h_d_out[i]) return set_err(c, CKKS_ERR_INVALID_ARG, "null ciphertext pointer");
+    const size_t N = c->N;
+    const u32 nb_max = n_ct < CT_BATCH ? n_ct : CT_BATCH;
+    const u32 l1 = level - 1, l2 = level - 2, l3 = level - 3;
+    const size_t xs = (size_t)(level + 1) * N;  // component stride of x
+    const size_t x2s = (size_t)(l1 + 1) * N, x3s = (size_t)(l2 + 1) * N, Bs = (size_t)(l3 + 1) * N;
+    Arena ar(d_ws, ws_bytes);
+    u64* x2 = ar.take(nb_max * 2 * x2s);        // level-1
+    u64* x3 = ar.take(nb_max * 2 * x3s);        // level-2
+    u64* x4 = ar.take(nb_max * 2 * x3s);        // level-2
+    u64* B = ar.take(nb_max * 2 * Bs);          // level-3
+    u64* tmp = ar.take(nb_max * 2 * xs);        // un-rescaled products
+    if (!ar.ok() || ar.used + ws_ctct(c, level, nb_max) + ws_rescale(c, level, nb_max) > ar.cap)
+        return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for the activation");
+    hipStream_t st = (hipStream_t)stream;
+    auto residues = [&](int64_t k, u32 lv, u64* out) {
+        for (u32 i = 0; i <= lv; i++) {
+            const u64 q = c->mod[i];
+            out[i] = k >= 0 ? (u64)k % q : (q - ((u64)(-k) % q)) % q;
+        }
+    };
+    u64 ka[CKKS_MAX_MODULI], kb[CKKS_MAX_MODULI];
+
+    for (u32 i0 = 0; i0 < n_ct; i0 += CT_BATCH) {
+        const u32 n = n_ct - i0 < CT_BATCH ? n_ct - i0 : CT_BATCH;
+        // pointer lists of this batch: inputs, and the per-item slices of the intermediates
+        const u64 *px[CT_BATCH], *px2[CT_BATCH], *px3[CT_BATCH], *px4[CT_BATCH], *pB[CT_BATCH], *ptmp[CT_BATCH];
+        u64 *ox2[CT_BATCH], *ox3[CT_BATCH], *ox4[CT_BATCH], *oB[CT_BATCH], *otmp[CT_BATCH], *oout[CT_BATCH];
+        for (u32 b = 0; b < n; b++) {
+            px[b] = (const u64*)h_d_x[i0 + b];
+            px2[b] = ox2[b] = x2 + b * 2 * x2s;
+            px3[b] = ox3[b] = x3 + b * 2 * x3s;
+            px4[b] = ox4[b] = x4 + b * 2 * x3s;
+            pB[b] = oB[b] = B + b * 2 * Bs;
+            oout[b] = (u64*)h_d_out[i0 + b];
+        }
+        auto tmp_at = [&](size_t cstride) {  // un-rescaled results, compact at the level that produced them
+            for (u32 b = 0; b < n; b++) ptmp[b] = otmp[b] = tmp + b * 2 * cstride;
+        };
+        int rc;
+        // x2 = Rescale(x * x)                                  level -> level-1
+        tmp_at(xs);
+        if ((rc = run_ctct(c, level, px, xs, px, xs, rlk->d_key, otmp, n, ar.rest(), st))) return rc;
+        if ((rc = run_rescale(c, level, ptmp, xs, ox2, n, ar.rest(), st))) return rc;
+        // x3 = Rescale(x2 * x), x4 = Rescale(x2 * x2)           level-1 -> level-2
+        tmp_at(x2s);
+        if ((rc = run_ctct(c, l1, px2, x2s, px, xs, rlk->d_key, otmp, n, ar.rest(), st))) return rc;
+        if ((rc = run_rescale(c, l1, ptmp, x2s, ox3, n, ar.rest(), st))) return rc;
+        if ((rc = run_ctct(c, l1, px2, x2s, px2, x2s, rlk->d_key, otmp, n, ar.rest(), st))) return rc;
+        if ((rc = run_rescale(c, l1, ptmp, x2s, ox4, n, ar.rest(), st))) return rc;
+        // B = Rescale(k5 * x + k7 * x3)                         level-2 -> level-3
+        residues(h_k[2], l2, ka);
+        residues(h_k[3], l2, kb);
+        tmp_at(x3s);
+        HIP_TRY(launch_lincomb2(c, l2, ptr_list(px, n), xs, ka, ptr_list(px3, n), x3s, kb, nullptr, 0, tmp, 2 * x3s, n, st));
+        if ((rc = run_rescale(c, l2, ptmp, x3s, oB, n, ar.rest(), st))) return rc;
+        // y = Rescale((k1 * x + k3 * x3) + x4 * B)              level-3 -> level-4
+        u64* prod = x2;  // x2 is no longer needed; n * [2][l3+1][N] fits in it
+        u64* oprod[CT_BATCH];
+        for (u32 b = 0; b < n; b++) oprod[b] = prod + b * 2 * Bs;
+        if ((rc = run_ctct(c, l3, px4, x3s, pB, Bs, rlk->d_key, oprod, n, ar.rest(), st))) return rc;
+        residues(h_k[0], l3, ka);
+        residues(h_k[1], l3, kb);
+        tmp_at(Bs);
+        HIP_TRY(launch_lincomb2(c, l3, ptr_list(px, n), xs, ka, ptr_list(px3, n), x3s, kb, prod, 2 * Bs, tmp, 2 * Bs, n, st));
+        if ((rc = run_rescale(c, l3, ptmp, Bs, oout, n, ar.rest(), st))) return rc;
     }
     return CKKS_OK;
 }
@@ -491,61 +598,6 @@ int ckks_prof_end(ckks_ctx* c, double* h_ms, uint64_t* h_launches, double* h_byt
     for (hipEvent_t ev : p->events) (void)hipEventDestroy(ev);
     delete p;
     return rc;
-}
-
-int he_poly_act_deg7(const ckks_ctx* c, const uint64_t* d_x, uint32_t level, const int64_t* h_k, const ckks_key* rlk,
-                     uint64_t* d_out, void* d_ws, size_t ws_bytes, void* stream) {
-    if (!c) return CKKS_ERR_INVALID_ARG;
-    if (!d_x || !h_k || !d_out) return set_err(c, CKKS_ERR_INVALID_ARG, "null pointer");
-    if (!c->dnum) return set_err(c, CKKS_ERR_UNSUPPORTED_PARAMS, "context has no key-switching digits");
-    if (!rlk) return set_err(c, CKKS_ERR_NO_KEY, "no relinearisation key");
-    if (rlk->galois_elt != 0) return set_err(c, CKKS_ERR_NO_KEY, "key is a rotation key, not the relinearisation key");
-    if (!level_ok(c, level) || level < 4) return set_err(c, CKKS_ERR_LEVEL_MISMATCH, "activation needs 4 <= level < num_q");
-    const size_t N = c->N;
-    Arena ar(d_ws, ws_bytes);
-    u64* x2 = ar.take(2 * (size_t)level * N);         // level-1
-    u64* x3 = ar.take(2 * (size_t)(level - 1) * N);   // level-2
-    u64* x4 = ar.take(2 * (size_t)(level - 1) * N);   // level-2
-    u64* B = ar.take(2 * (size_t)(level - 2) * N);    // level-3
-    u64* tmp = ar.take(2 * (size_t)(level + 1) * N);  // un-rescaled products
-    if (!ar.ok() || ar.used + ws_ctct(c, level) + ws_rescale(c, level) > ar.cap)
-        return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for the activation");
-    hipStream_t st = (hipStream_t)stream;
-    const u64* x = (const u64*)d_x;
-    const size_t xs = (size_t)(level + 1) * N;  // component stride of x
-    auto scratch = [&]() { return Arena(ar.base + ar.used, ar.cap - ar.used); };
-    auto residues = [&](int64_t k, u32 lv, u64* out) {
-        for (u32 i = 0; i <= lv; i++) {
-            const u64 q = c->mod[i];
-            out[i] = k >= 0 ? (u64)k % q : (q - ((u64)(-k) % q)) % q;
-        }
-    };
-    int rc;
-    // x2 = Rescale(x * x)                                  level -> level-1
-    { Arena s = scratch(); if ((rc = run_ctct(c, level, x, xs, x, xs, rlk->d_key, tmp, s, st))) return rc; }
-    { Arena s = scratch(); if ((rc = run_rescale(c, level, tmp, xs, x2, s, st))) return rc; }
-    const u32 l1 = level - 1, l2 = level - 2, l3 = level - 3;
-    const size_t x2s = (size_t)(l1 + 1) * N, x3s = (size_t)(l2 + 1) * N;
-    // x3 = Rescale(x2 * x), x4 = Rescale(x2 * x2)           level-1 -> level-2
-    { Arena s = scratch(); if ((rc = run_ctct(c, l1, x2, x2s, x, xs, rlk->d_key, tmp, s, st))) return rc; }
-    { Arena s = scratch(); if ((rc = run_rescale(c, l1, tmp, x2s, x3, s, st))) return rc; }
-    { Arena s = scratch(); if ((rc = run_ctct(c, l1, x2, x2s, x2, x2s, rlk->d_key, tmp, s, st))) return rc; }
-    { Arena s = scratch(); if ((rc = run_rescale(c, l1, tmp, x2s, x4, s, st))) return rc; }
-    // B = Rescale(k5 * x + k7 * x3)                         level-2 -> level-3
-    u64 ka[CKKS_MAX_MODULI], kb[CKKS_MAX_MODULI];
-    residues(h_k[2], l2, ka);
-    residues(h_k[3], l2, kb);
-    HIP_TRY(launch_lincomb2(c, l2, x, xs, ka, x3, x3s, kb, nullptr, tmp, st));
-    { Arena s = scratch(); if ((rc = run_rescale(c, l2, tmp, x3s, B, s, st))) return rc; }
-    // y = Rescale((k1 * x + k3 * x3) + x4 * B)              level-3 -> level-4
-    const size_t Bs = (size_t)(l3 + 1) * N;
-    u64* prod = x2;  // x2 is no longer needed; [2][l3+1][N] fits in it
-    { Arena s = scratch(); if ((rc = run_ctct(c, l3, x4, x3s, B, Bs, rlk->d_key, prod, s, st))) return rc; }
-    residues(h_k[0], l3, ka);
-    residues(h_k[1], l3, kb);
-    HIP_TRY(launch_lincomb2(c, l3, x, xs, ka, x3, x3s, kb, prod, tmp, st));
-    { Arena s = scratch(); if ((rc = run_rescale(c, l3, tmp, Bs, (u64*)d_out, s, st))) return rc; }
-    return CKKS_OK;
 }
 
 }  // extern "C"

@@ -104,6 +104,9 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
     c->log_hi = p->log_n - c->log_lo;
     c->lazy_terms = 1u << (lazy_log > 12 ? 12 : lazy_log);
     c->small_q = bmax <= 50;
+    auto pad = [](u32 v) { return v <= 4 ? 4u : (v <= 8 ? 8u : 16u); };
+    c->alpha_pad = pad(alpha);
+    c->k_pad = pad(p->num_p);
     c->mod.assign(p->moduli, p->moduli + M);
     c->psi.assign(p->psi, p->psi + M);
 
@@ -147,39 +150,39 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
                     for (u32 b = lo; b < hi; b++) if (b != lo + a) qhat = h_mulmod(qhat, c->mod[b] % qa, qa);
                     const u64 inv = h_invmod(qhat, qa);
                     tab[a] = inv;
-                    tab[alpha + a] = h_shoup(inv, qa);
+                    tab[c->alpha_pad + a] = h_shoup(inv, qa);
                     for (u32 e = 0; e < E; e++) {
                         const u64 qt = c->mod[c->ext_modulus(level, e)];
                         u64 v = 1;
                         for (u32 b = lo; b < hi; b++) if (b != lo + a) v = h_mulmod(v, c->mod[b] % qt, qt);
-                        tab[2 * alpha + (size_t)a * M + e] = v;
+                        tab[2 * c->alpha_pad + (size_t)e * c->alpha_pad + a] = v;
                     }
                 }
                 for (u32 e = 0; e < E; e++) {  // -Q_j mod t: one per centred digit limb that is negative
                     const u64 qt = c->mod[c->ext_modulus(level, e)];
                     u64 Q = 1;
                     for (u32 b = lo; b < hi; b++) Q = h_mulmod(Q, c->mod[b] % qt, qt);
-                    tab[(size_t)alpha * (2 + M) + e] = (qt - Q) % qt;
+                    tab[c->modup_negq_off() + e] = (qt - Q) % qt;
                 }
             }
     }
     // ModDown table
     std::vector<u64> moddown;
     if (c->dnum) {
-        const u32 k = c->num_p, nq = c->num_q;
-        moddown.assign(2 * k + (size_t)k * nq + 3 * nq, 0);
+        const u32 k = c->num_p, nq = c->num_q, kp = c->k_pad;
+        moddown.assign(2 * kp + (size_t)kp * nq + 3 * nq, 0);
         for (u32 a = 0; a < k; a++) {
             const u64 pa = c->mod[nq + a];
             u64 phat = 1;
             for (u32 b = 0; b < k; b++) if (b != a) phat = h_mulmod(phat, c->mod[nq + b] % pa, pa);
             const u64 inv = h_invmod(phat, pa);
             moddown[a] = inv;
-            moddown[k + a] = h_shoup(inv, pa);
+            moddown[kp + a] = h_shoup(inv, pa);
             for (u32 i = 0; i < nq; i++) {
                 const u64 qi = c->mod[i];
                 u64 v = 1;
                 for (u32 b = 0; b < k; b++) if (b != a) v = h_mulmod(v, c->mod[nq + b] % qi, qi);
-                moddown[2 * k + (size_t)a * nq + i] = v;
+                moddown[2 * kp + (size_t)i * kp + a] = v;
             }
         }
         for (u32 i = 0; i < nq; i++) {
@@ -187,9 +190,9 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
             u64 P = 1;
             for (u32 b = 0; b < k; b++) P = h_mulmod(P, c->mod[nq + b] % qi, qi);
             const u64 pinv = h_invmod(P, qi);
-            moddown[2 * k + (size_t)k * nq + i] = pinv;
-            moddown[2 * k + (size_t)k * nq + nq + i] = h_shoup(pinv, qi);
-            moddown[2 * k + (size_t)k * nq + 2 * nq + i] = (qi - P) % qi;  // -P mod q_i
+            moddown[2 * kp + (size_t)kp * nq + i] = pinv;
+            moddown[2 * kp + (size_t)kp * nq + nq + i] = h_shoup(pinv, qi);
+            moddown[2 * kp + (size_t)kp * nq + 2 * nq + i] = (qi - P) % qi;  // -P mod q_i
         }
     }
     // rescale table [l][i] = (q_l^-1 mod q_i, Shoup companion, q_l mod q_i)

@@ -41,8 +41,17 @@ struct ProfState {
     double ops[K_COUNT] = {0};    // modular multiplications (butterflies, multiply-adds) of the recorded launches
 };
 
+// Batched kernels take up to KS_MAX_BATCH items; item b's operand starts at p[b].
+#define KS_MAX_BATCH 16   // pointer-list capacity; ciphertext batches are at most CT_BATCH = 8 (two components each)
+#define CT_BATCH 8
+struct PtrList8 {
+    const u64* p[KS_MAX_BATCH];
+};
+struct OutList8 {
+    u64* p[KS_MAX_BATCH];
+};
+
 // One key switch of a batch, as its last kernel sees it (see moddown_final_kernel).
-#define KS_MAX_BATCH 8
 struct FinalItem {
     const u64* add0;
     const u64* add1;
@@ -73,7 +82,7 @@ struct ckks_ctx {
     TwPair* d_tw = nullptr;           // [M][N]  psi^bitrev(i) with its Shoup companion
     TwPair* d_itw = nullptr;          // [M][N]  psi^-bitrev(i) with its Shoup companion
     u64* d_modup = nullptr;           // per level, per digit: see modup_digit_stride()
-    u64* d_moddown = nullptr;         // phat_inv[k], phat_inv_sh[k], phat_q[k][num_q], pinv[num_q], pinv_sh[num_q], negp[num_q]
+    u64* d_moddown = nullptr;         // phat_inv[k_pad], phat_inv_sh[k_pad], phat_q[num_q][k_pad], pinv[num_q], pinv_sh[num_q], negp[num_q]
     u64* d_rescale = nullptr;         // [num_q][num_q][3]: (q_l^-1 mod q_i, its Shoup companion, q_l mod q_i)
 
     mutable std::string err;
@@ -84,9 +93,13 @@ struct ckks_ctx {
     u32 digit_lo(u32 j) const { return j * alpha; }
     u32 digit_hi(u32 j, u32 level) const { u32 h = (j + 1) * alpha; return h < level + 1 ? h : level + 1; }
     u32 ext_modulus(u32 level, u32 e) const { return e <= level ? e : num_q + (e - level - 1); }
-    // ModUp table of one digit: inv[alpha], inv_sh[alpha], conv[alpha][M], negq[M] (conv and negq
-    // indexed by the position e in the extended basis of that level; negq = -Q_j mod t)
-    size_t modup_digit_stride() const { return (size_t)alpha * (2 + M) + M; }
+    // ModUp table of one digit: inv[alpha_pad], inv_sh[alpha_pad], conv[M][alpha_pad], negq[M] (conv and negq
+    // indexed by the position e in the extended basis of that level; negq = -Q_j mod t).  The alpha
+    // constants of one target limb are adjacent so that a wavefront fetches them with one wide scalar load.
+    // Rows are padded to alpha_pad / k_pad entries (4, 8 or 16; zeros beyond the real ones).
+    u32 alpha_pad, k_pad;
+    size_t modup_negq_off() const { return (size_t)alpha_pad * (2 + M); }
+    size_t modup_digit_stride() const { return modup_negq_off() + ((M + 15) / 16) * 16; }
     size_t modup_level_stride() const { return modup_digit_stride() * dnum; }
     const u64* modup_table(u32 level, u32 j) const { return d_modup + level * modup_level_stride() + j * modup_digit_stride(); }
 };
@@ -113,12 +126,16 @@ struct ProfScope {
 };
 
 // ---- kernel launchers (each enqueues on `st` and returns the launch status) -------------------
-// ntt.hip
+// ntt.hip: batch x pl.n limb-polys; item b reads src + b*src_bstride*N (or src_ptrs[b] when given: host
+// array of `batch` <= KS_MAX_BATCH device pointers) and writes dst + b*dst_bstride*N
 hipError_t launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, size_t src_bstride, u64* dst,
-                      size_t dst_bstride, const PolyList& pl, u32 batch, hipStream_t st);
+                      size_t dst_bstride, const PolyList& pl, u32 batch, hipStream_t st, const u64* const* src_ptrs = nullptr);
 // keyswitch.hip
-hipError_t launch_modup_conv(const ckks_ctx* c, u32 level, u32 j, const u64* y, const u64* c_in, u64* digit, hipStream_t st);
+hipError_t launch_modup_conv(const ckks_ctx* c, u32 level, u32 j, const u64* y, size_t y_bstride, const PtrList8& c_in, u64* digit,
+                             size_t digit_bstride, u32 n, hipStream_t st);
 hipError_t launch_key_inner(const ckks_ctx* c, u32 level, const u64* digits, const u64* key, u32 g, u64* v, hipStream_t st);
+hipError_t launch_key_inner_multi(const ckks_ctx* c, u32 level, const u64* digits, size_t digits_bstride, const u64* key, u32 g,
+                                  u64* v, size_t v_bstride, u32 n, hipStream_t st);
 hipError_t launch_moddown_conv(const ckks_ctx* c, u32 level, const u64* v, u64* w, u32 batch, hipStream_t st);
 hipError_t launch_moddown_final(const ckks_ctx* c, u32 level, const u64* v, const u64* w, const FinalItem* items, u32 n, hipStream_t st);
 // pointwise.hip
@@ -126,13 +143,15 @@ hipError_t launch_automorph(const ckks_ctx* c, u32 n_polys, const u64* in, u32 g
 hipError_t launch_copy(const u64* in, u64* out, size_t n, hipStream_t st);
 hipError_t launch_ptct_mac(const ckks_ctx* c, u32 level, const u64* const* pts, const u64* const* cts, u32 n_terms, u64* acc,
                            int accumulate, hipStream_t st);
-hipError_t launch_rescale_conv(const ckks_ctx* c, u32 level, const u64* r, u64* w, hipStream_t st);
-hipError_t launch_rescale_final(const ckks_ctx* c, u32 level, const u64* ct, size_t ct_cstride, const u64* w, u64* out, hipStream_t st);
-hipError_t launch_tensor(const ckks_ctx* c, u32 level, const u64* a, size_t a_cstride, const u64* b, size_t b_cstride, u64* d0,
-                         u64* d1, u64* d2, hipStream_t st);
+hipError_t launch_rescale_conv(const ckks_ctx* c, u32 level, const u64* r, u64* w, u32 batch, hipStream_t st);
+hipError_t launch_rescale_final(const ckks_ctx* c, u32 level, const PtrList8& ct, size_t ct_cstride, const u64* w, const OutList8& out,
+                                u32 n, hipStream_t st);
+hipError_t launch_tensor(const ckks_ctx* c, u32 level, const PtrList8& a, size_t a_cstride, const PtrList8& b, size_t b_cstride,
+                         u64* d0, u64* d1, u64* d2, u32 n, hipStream_t st);
 hipError_t launch_mask_mul(const ckks_ctx* c, u32 level, const u64* mask, const u64* ct, u64* out, hipStream_t st);
 size_t weighted_sum_scratch_elems(const ckks_ctx* c, u32 level, u32 n_terms, u32 c_out);
 hipError_t launch_weighted_sum(const ckks_ctx* c, u32 level, const u64* xs, u32 n_terms, const u64* w_res, u32 c_out, u64* acc,
                                u64* scratch, hipStream_t st);
-hipError_t launch_lincomb2(const ckks_ctx* c, u32 level, const u64* a, size_t a_cstride, const u64* ka, const u64* b,
-                           size_t b_cstride, const u64* kb, const u64* add, u64* out, hipStream_t st);
+hipError_t launch_lincomb2(const ckks_ctx* c, u32 level, const PtrList8& a, size_t a_cstride, const u64* ka, const PtrList8& b,
+                           size_t b_cstride, const u64* kb, const u64* add, size_t add_bstride, u64* out, size_t out_bstride, u32 n,
+                           hipStream_t st);

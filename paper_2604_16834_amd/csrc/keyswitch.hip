@@ -29,12 +29,15 @@ __device__ __forceinline__ u32 galois_gather_index(u32 k, u32 g, u32 log_n) {
 // c_in  [level+1][N] the polynomial being switched, NTT form (source of the digit's own limbs)
 // digit [E][N]       out: own limbs copied (NTT form), other limbs in coefficient form
 #define MODUP_LIMBS_PER_BLOCK 4
-__global__ __launch_bounds__(KS_THREADS) void modup_conv_kernel(const u64* __restrict__ y, const u64* __restrict__ c_in,
-                                                                u64* __restrict__ digit, const u64* __restrict__ tab,
-                                                                const ModConst* __restrict__ mc, u32 N, u32 level, u32 num_q,
-                                                                u32 lo, u32 nd, u32 alpha, u32 M, u32 E) {
+__global__ __launch_bounds__(KS_THREADS) void modup_conv_kernel(const u64* __restrict__ y, size_t y_bstride, PtrList8 c_list,
+                                                                u64* __restrict__ digit, size_t digit_bstride,
+                                                                const u64* __restrict__ tab, const ModConst* __restrict__ mc, u32 N,
+                                                                u32 level, u32 num_q, u32 lo, u32 nd, u32 alpha, u32 M, u32 E) {
     const u32 x = blockIdx.x * KS_THREADS + threadIdx.x;
     if (x >= N) return;
+    y += blockIdx.z * y_bstride;
+    digit += blockIdx.z * digit_bstride;
+    const u64* __restrict__ c_in = c_list.p[blockIdx.z];
     u64 yv[KS_MAX_DIGIT];
     u64 n_neg = 0;
 #pragma unroll
@@ -44,7 +47,7 @@ __global__ __launch_bounds__(KS_THREADS) void modup_conv_kernel(const u64* __res
             yv[a] = mul_shoup(y[(size_t)a * N + x], tab[a], tab[alpha + a], qa);
             n_neg += yv[a] > (qa >> 1) ? 1 : 0;
         }
-    const u64* negq = tab + (size_t)alpha * (2 + M);
+    const u64* negq = tab + (size_t)alpha * (2 + M);  // alpha = padded row length here
     const u32 e0 = blockIdx.y * MODUP_LIMBS_PER_BLOCK;
     for (u32 e = e0; e < e0 + MODUP_LIMBS_PER_BLOCK && e < E; e++) {
         const u32 t = e <= level ? e : num_q + (e - level - 1);
@@ -55,30 +58,38 @@ __global__ __launch_bounds__(KS_THREADS) void modup_conv_kernel(const u64* __res
         U128 acc = {0, 0};
 #pragma unroll
         for (u32 a = 0; a < KS_MAX_DIGIT; a++)
-            if (a < nd) acc_wide(acc, yv[a], tab[2 * alpha + (size_t)a * M + e]);
+            if (a < nd) acc_wide(acc, yv[a], tab[2 * alpha + (size_t)e * alpha + a]);
         acc_wide(acc, n_neg, negq[e]);
         digit[(size_t)e * N + x] = barrett_reduce(acc, mc[t]);
     }
 }
 
-// ModUp for moduli below 2^50: carry-free 25-bit-split accumulation (three multiply-adds per term)
-__global__ __launch_bounds__(KS_THREADS) void modup_conv50_kernel(const u64* __restrict__ y, const u64* __restrict__ c_in,
-                                                                  u64* __restrict__ digit, const u64* __restrict__ tab,
-                                                                  const ModConst* __restrict__ mc, u32 N, u32 level, u32 num_q,
-                                                                  u32 lo, u32 nd, u32 alpha, u32 M, u32 E) {
+// ModUp for moduli below 2^50: carry-free 25-bit-split accumulation (three multiply-adds per term).
+// AP = padded digit size: the AP constants of a target limb are one aligned run (wide scalar load).
+template <int AP>
+__global__ __launch_bounds__(KS_THREADS) void modup_conv50_kernel(const u64* __restrict__ y, size_t y_bstride, PtrList8 c_list,
+                                                                  u64* __restrict__ digit, size_t digit_bstride,
+                                                                  const u64* __restrict__ tab, const ModConst* __restrict__ mc, u32 N,
+                                                                  u32 level, u32 num_q, u32 lo, u32 nd, u32 M, u32 E) {
     const u32 x = blockIdx.x * KS_THREADS + threadIdx.x;
     if (x >= N) return;
-    Split50 yv[KS_MAX_DIGIT];
+    y += blockIdx.z * y_bstride;
+    digit += blockIdx.z * digit_bstride;
+    const u64* __restrict__ c_in = c_list.p[blockIdx.z];
+    Split50 yv[AP];
     u32 n_neg = 0;
 #pragma unroll
-    for (u32 a = 0; a < KS_MAX_DIGIT; a++)
+    for (u32 a = 0; a < AP; a++) {
+        yv[a] = {0, 0, 0};
         if (a < nd) {
             const u64 qa = mc[lo + a].q;
-            const u64 v = mul_shoup(y[(size_t)a * N + x], tab[a], tab[alpha + a], qa);
+            const u64 v = mul_shoup(y[(size_t)a * N + x], tab[a], tab[AP + a], qa);
             n_neg += v > (qa >> 1) ? 1 : 0;
             yv[a] = split50(v);
         }
-    const u64* negq = tab + (size_t)alpha * (2 + M);
+    }
+    const u64* conv = (const u64*)__builtin_assume_aligned(tab + 2 * AP, 8 * AP);
+    const u64* negq = tab + (size_t)AP * (2 + M);
     const u32 e0 = blockIdx.y * MODUP_LIMBS_PER_BLOCK;
     for (u32 e = e0; e < e0 + MODUP_LIMBS_PER_BLOCK && e < E; e++) {
         const u32 t = e <= level ? e : num_q + (e - level - 1);
@@ -86,27 +97,37 @@ __global__ __launch_bounds__(KS_THREADS) void modup_conv50_kernel(const u64* __r
             digit[(size_t)e * N + x] = c_in[(size_t)t * N + x];
             continue;
         }
+        const u64* ce = (const u64*)__builtin_assume_aligned(conv + (size_t)e * AP, 8 * AP);
+        u64 cv[AP];
+#pragma unroll
+        for (u32 a = 0; a < AP; a++) cv[a] = ce[a];
         Acc50 acc = {0, 0, 0};
 #pragma unroll
-        for (u32 a = 0; a < KS_MAX_DIGIT; a++)
-            if (a < nd) acc50_mad(acc, yv[a], split50(tab[2 * alpha + (size_t)a * M + e]));
+        for (u32 a = 0; a < AP; a++) acc50_mad(acc, yv[a], split50(cv[a]));
         U128 v = acc50_value(acc);
         acc_wide(v, n_neg, negq[e]);
         digit[(size_t)e * N + x] = barrett_reduce(v, mc[t]);
     }
 }
 
-hipError_t launch_modup_conv(const ckks_ctx* c, u32 level, u32 j, const u64* y, const u64* c_in, u64* digit, hipStream_t st) {
+// n <= KS_MAX_BATCH polynomials at once: item b reads y + b*y_bstride and c_in.p[b], writes digit + b*digit_bstride
+hipError_t launch_modup_conv(const ckks_ctx* c, u32 level, u32 j, const u64* y, size_t y_bstride, const PtrList8& c_in, u64* digit,
+                             size_t digit_bstride, u32 n, hipStream_t st) {
     const u32 E = c->ext_limbs(level), lo = c->digit_lo(j), nd = c->digit_hi(j, level) - lo;
-    dim3 grid((c->N + KS_THREADS - 1) / KS_THREADS, (E + MODUP_LIMBS_PER_BLOCK - 1) / MODUP_LIMBS_PER_BLOCK);
+    dim3 grid((c->N + KS_THREADS - 1) / KS_THREADS, (E + MODUP_LIMBS_PER_BLOCK - 1) / MODUP_LIMBS_PER_BLOCK, n);
+    const u64* tab = c->modup_table(level, j);
+    ProfScope ps__(c, K_MODUP_CONV, st, 8.0 * n * c->N * (2.0 * nd + E), (double)n * c->N * nd * (1.0 + E - nd));
     if (c->small_q) {
-        ProfScope ps__(c, K_MODUP_CONV, st, 8.0 * c->N * (2.0 * nd + E), (double)c->N * nd * (1.0 + E - nd));
-        hipLaunchKernelGGL(modup_conv50_kernel, grid, dim3(KS_THREADS), 0, st, y, c_in, digit, c->modup_table(level, j), c->d_mc,
-                           c->N, level, c->num_q, lo, nd, c->alpha, c->M, E);
-        return hipGetLastError();
+        if (c->alpha_pad == 4)
+            hipLaunchKernelGGL(modup_conv50_kernel<4>, grid, dim3(KS_THREADS), 0, st, y, y_bstride, c_in, digit, digit_bstride, tab, c->d_mc, c->N, level, c->num_q, lo, nd, c->M, E);
+        else if (c->alpha_pad == 8)
+            hipLaunchKernelGGL(modup_conv50_kernel<8>, grid, dim3(KS_THREADS), 0, st, y, y_bstride, c_in, digit, digit_bstride, tab, c->d_mc, c->N, level, c->num_q, lo, nd, c->M, E);
+        else
+            hipLaunchKernelGGL(modup_conv50_kernel<16>, grid, dim3(KS_THREADS), 0, st, y, y_bstride, c_in, digit, digit_bstride, tab, c->d_mc, c->N, level, c->num_q, lo, nd, c->M, E);
+    } else {
+        hipLaunchKernelGGL(modup_conv_kernel, grid, dim3(KS_THREADS), 0, st, y, y_bstride, c_in, digit, digit_bstride, tab, c->d_mc,
+                           c->N, level, c->num_q, lo, nd, c->alpha_pad, c->M, E);
     }
-    { ProfScope ps__(c, K_MODUP_CONV, st, 8.0 * c->N * (2.0 * nd + E), (double)c->N * nd * (1.0 + E - nd)); hipLaunchKernelGGL(modup_conv_kernel, grid, dim3(KS_THREADS), 0, st, y, c_in, digit, c->modup_table(level, j), c->d_mc,
-                       c->N, level, c->num_q, lo, nd, c->alpha, c->M, E); }
     return hipGetLastError();
 }
 
@@ -144,12 +165,55 @@ hipError_t launch_key_inner(const ckks_ctx* c, u32 level, const u64* digits, con
     return hipGetLastError();
 }
 
+// The same key applied to n <= KS_MAX_BATCH sets of digits (the channels of a layer share their
+// rotation and relinearisation keys): every thread keeps its key words while it walks the batch, so
+// the key streams from HBM once per batch instead of once per key switch.
+// digits + b*digits_bstride: [beta][E][N];  v + b*v_bstride: [2][E][N]
+__global__ __launch_bounds__(KS_THREADS) void key_inner_multi_kernel(const u64* __restrict__ digits, size_t digits_bstride,
+                                                                     const u64* __restrict__ key, u64* __restrict__ v,
+                                                                     size_t v_bstride, const ModConst* __restrict__ mc, u32 log_n,
+                                                                     u32 level, u32 num_q, u32 M, u32 E, u32 beta, u32 g, u32 n) {
+    const u32 N = 1u << log_n;
+    const u32 x = blockIdx.x * KS_THREADS + threadIdx.x;
+    if (x >= N) return;
+    const u32 e = blockIdx.y;
+    const u32 t = e <= level ? e : num_q + (e - level - 1);
+    const u32 xs = g == 1 ? x : galois_gather_index(x, g, log_n);
+    const ModConst m = mc[t];
+    for (u32 b = 0; b < n; b++) {
+        const u64* d = digits + b * digits_bstride;
+        U128 acc0 = {0, 0}, acc1 = {0, 0};
+        for (u32 j = 0; j < beta; j++) {
+            const u64 dv = d[((size_t)j * E + e) * N + xs];
+            acc_wide(acc0, dv, key[(((size_t)j * 2 + 0) * M + t) * N + x]);
+            acc_wide(acc1, dv, key[(((size_t)j * 2 + 1) * M + t) * N + x]);
+            if ((j & 15) == 15) {
+                acc0.lo = barrett_reduce(acc0, m); acc0.hi = 0;
+                acc1.lo = barrett_reduce(acc1, m); acc1.hi = 0;
+            }
+        }
+        u64* vb = v + b * v_bstride;
+        vb[((size_t)0 * E + e) * N + x] = barrett_reduce(acc0, m);
+        vb[((size_t)1 * E + e) * N + x] = barrett_reduce(acc1, m);
+    }
+}
+
+hipError_t launch_key_inner_multi(const ckks_ctx* c, u32 level, const u64* digits, size_t digits_bstride, const u64* key, u32 g,
+                                  u64* v, size_t v_bstride, u32 n, hipStream_t st) {
+    const u32 E = c->ext_limbs(level), beta = c->live_digits(level);
+    dim3 grid((c->N + KS_THREADS - 1) / KS_THREADS, E);
+    ProfScope ps__(c, K_KEY_INNER, st, 8.0 * c->N * E * (2.0 * beta + n * (beta + 2.0)), 2.0 * n * c->N * E * beta);
+    hipLaunchKernelGGL(key_inner_multi_kernel, grid, dim3(KS_THREADS), 0, st, digits, digits_bstride, key, v, v_bstride, c->d_mc,
+                       c->log_n, level, c->num_q, c->M, E, beta, g, n);
+    return hipGetLastError();
+}
+
 // ---- ModDown, conversion of the P-part ----------------------------------------------------------
 // v [2][E][N]: limbs level+1.. hold the P-part in coefficient form.  w [2][level+1][N] (coefficients)
 #define MODDOWN_LIMBS_PER_BLOCK 4
 __global__ __launch_bounds__(KS_THREADS) void moddown_conv_kernel(const u64* __restrict__ v, u64* __restrict__ w,
                                                                   const u64* __restrict__ tab, const ModConst* __restrict__ mc,
-                                                                  u32 N, u32 level, u32 num_q, u32 k, u32 E) {
+                                                                  u32 N, u32 level, u32 num_q, u32 k, u32 kp, u32 E) {
     const u32 x = blockIdx.x * KS_THREADS + threadIdx.x;
     if (x >= N) return;
     const u32 comp = blockIdx.z;
@@ -159,46 +223,52 @@ __global__ __launch_bounds__(KS_THREADS) void moddown_conv_kernel(const u64* __r
     for (u32 a = 0; a < KS_MAX_DIGIT; a++)
         if (a < k) {
             const u64 pa = mc[num_q + a].q;
-            z[a] = mul_shoup(v[((size_t)comp * E + level + 1 + a) * N + x], tab[a], tab[k + a], pa);
+            z[a] = mul_shoup(v[((size_t)comp * E + level + 1 + a) * N + x], tab[a], tab[kp + a], pa);
             n_neg += z[a] > (pa >> 1) ? 1 : 0;
         }
-    const u64* phat_q = tab + 2 * k;  // [k][num_q]
-    const u64* negp = tab + 2 * k + (size_t)k * num_q + 2 * num_q;
+    const u64* phat_q = tab + 2 * kp;  // [num_q][kp]
+    const u64* negp = tab + 2 * kp + (size_t)kp * num_q + 2 * num_q;
     const u32 i0 = blockIdx.y * MODDOWN_LIMBS_PER_BLOCK;
     for (u32 i = i0; i < i0 + MODDOWN_LIMBS_PER_BLOCK && i <= level; i++) {
         U128 acc = {0, 0};
 #pragma unroll
         for (u32 a = 0; a < KS_MAX_DIGIT; a++)
-            if (a < k) acc_wide(acc, z[a], phat_q[(size_t)a * num_q + i]);
+            if (a < k) acc_wide(acc, z[a], phat_q[(size_t)i * kp + a]);
         acc_wide(acc, n_neg, negp[i]);
         w[((size_t)comp * (level + 1) + i) * N + x] = barrett_reduce(acc, mc[i]);
     }
 }
 
+template <int KP>
 __global__ __launch_bounds__(KS_THREADS) void moddown_conv50_kernel(const u64* __restrict__ v, u64* __restrict__ w,
                                                                     const u64* __restrict__ tab, const ModConst* __restrict__ mc,
                                                                     u32 N, u32 level, u32 num_q, u32 k, u32 E) {
     const u32 x = blockIdx.x * KS_THREADS + threadIdx.x;
     if (x >= N) return;
     const u32 comp = blockIdx.z;
-    Split50 z[KS_MAX_DIGIT];
+    Split50 z[KP];
     u32 n_neg = 0;
 #pragma unroll
-    for (u32 a = 0; a < KS_MAX_DIGIT; a++)
+    for (u32 a = 0; a < KP; a++) {
+        z[a] = {0, 0, 0};
         if (a < k) {
             const u64 pa = mc[num_q + a].q;
-            const u64 zv = mul_shoup(v[((size_t)comp * E + level + 1 + a) * N + x], tab[a], tab[k + a], pa);
+            const u64 zv = mul_shoup(v[((size_t)comp * E + level + 1 + a) * N + x], tab[a], tab[KP + a], pa);
             n_neg += zv > (pa >> 1) ? 1 : 0;
             z[a] = split50(zv);
         }
-    const u64* phat_q = tab + 2 * k;
-    const u64* negp = tab + 2 * k + (size_t)k * num_q + 2 * num_q;
+    }
+    const u64* phat_q = (const u64*)__builtin_assume_aligned(tab + 2 * KP, 8 * KP);  // [num_q][KP]
+    const u64* negp = tab + 2 * KP + (size_t)KP * num_q + 2 * num_q;
     const u32 i0 = blockIdx.y * MODDOWN_LIMBS_PER_BLOCK;
     for (u32 i = i0; i < i0 + MODDOWN_LIMBS_PER_BLOCK && i <= level; i++) {
+        const u64* pe = (const u64*)__builtin_assume_aligned(phat_q + (size_t)i * KP, 8 * KP);
+        u64 cv[KP];
+#pragma unroll
+        for (u32 a = 0; a < KP; a++) cv[a] = pe[a];
         Acc50 acc = {0, 0, 0};
 #pragma unroll
-        for (u32 a = 0; a < KS_MAX_DIGIT; a++)
-            if (a < k) acc50_mad(acc, z[a], split50(phat_q[(size_t)a * num_q + i]));
+        for (u32 a = 0; a < KP; a++) acc50_mad(acc, z[a], split50(cv[a]));
         U128 s = acc50_value(acc);
         acc_wide(s, n_neg, negp[i]);
         w[((size_t)comp * (level + 1) + i) * N + x] = barrett_reduce(s, mc[i]);
@@ -209,12 +279,16 @@ hipError_t launch_moddown_conv(const ckks_ctx* c, u32 level, const u64* v, u64* 
     dim3 grid((c->N + KS_THREADS - 1) / KS_THREADS, (level + 1 + MODDOWN_LIMBS_PER_BLOCK - 1) / MODDOWN_LIMBS_PER_BLOCK, batch);
     if (c->small_q) {
         ProfScope ps__(c, K_MODDOWN_CONV, st, 8.0 * batch * c->N * (c->num_p + level + 1.0), 1.0 * batch * c->N * c->num_p * (level + 2.0));
-        hipLaunchKernelGGL(moddown_conv50_kernel, grid, dim3(KS_THREADS), 0, st, v, w, c->d_moddown, c->d_mc, c->N, level, c->num_q,
-                           c->num_p, c->ext_limbs(level));
+        if (c->k_pad == 4)
+            hipLaunchKernelGGL(moddown_conv50_kernel<4>, grid, dim3(KS_THREADS), 0, st, v, w, c->d_moddown, c->d_mc, c->N, level, c->num_q, c->num_p, c->ext_limbs(level));
+        else if (c->k_pad == 8)
+            hipLaunchKernelGGL(moddown_conv50_kernel<8>, grid, dim3(KS_THREADS), 0, st, v, w, c->d_moddown, c->d_mc, c->N, level, c->num_q, c->num_p, c->ext_limbs(level));
+        else
+            hipLaunchKernelGGL(moddown_conv50_kernel<16>, grid, dim3(KS_THREADS), 0, st, v, w, c->d_moddown, c->d_mc, c->N, level, c->num_q, c->num_p, c->ext_limbs(level));
         return hipGetLastError();
     }
     { ProfScope ps__(c, K_MODDOWN_CONV, st, 8.0 * batch * c->N * (c->num_p + level + 1.0), 1.0 * batch * c->N * c->num_p * (level + 2.0)); hipLaunchKernelGGL(moddown_conv_kernel, grid, dim3(KS_THREADS), 0, st, v, w, c->d_moddown, c->d_mc, c->N, level,
-                       c->num_q, c->num_p, c->ext_limbs(level)); }
+                       c->num_q, c->num_p, c->k_pad, c->ext_limbs(level)); }
     return hipGetLastError();
 }
 
@@ -226,14 +300,14 @@ hipError_t launch_moddown_conv(const ckks_ctx* c, u32 level, const u64* v, u64* 
 __global__ __launch_bounds__(KS_THREADS) void moddown_final_kernel(const u64* __restrict__ v, const u64* __restrict__ w,
                                                                    FinalBatch B, const u64* __restrict__ tab,
                                                                    const ModConst* __restrict__ mc, u32 log_n, u32 level,
-                                                                   u32 num_q, u32 k, u32 E) {
+                                                                   u32 num_q, u32 kp, u32 E) {
     const u32 N = 1u << log_n;
     const u32 x = blockIdx.x * KS_THREADS + threadIdx.x;
     if (x >= N) return;
     const u32 i = blockIdx.y, b = blockIdx.z, comp = b & 1;
     const FinalItem it = B.it[b >> 1];
     const ModConst m = mc[i];
-    const u64* pinv = tab + 2 * k + (size_t)k * num_q;
+    const u64* pinv = tab + 2 * kp + (size_t)kp * num_q;
     u64 d = sub_mod(v[((size_t)b * E + i) * N + x], w[((size_t)b * (level + 1) + i) * N + x], m.q);
     u64 r = mul_shoup(d, pinv[i], pinv[num_q + i], m.q);
     const u64* add = comp == 0 ? it.add0 : it.add1;
@@ -259,6 +333,6 @@ hipError_t launch_moddown_final(const ckks_ctx* c, u32 level, const u64* v, cons
     dim3 grid((c->N + KS_THREADS - 1) / KS_THREADS, level + 1, 2 * n);
     ProfScope ps__(c, K_MODDOWN_FINAL, st, 8.0 * c->N * (level + 1.0) * (6.0 * n + extra), 2.0 * c->N * (level + 1.0) * n);
     hipLaunchKernelGGL(moddown_final_kernel, grid, dim3(KS_THREADS), 0, st, v, w, B, c->d_moddown, c->d_mc, c->log_n, level,
-                       c->num_q, c->num_p, c->ext_limbs(level));
+                       c->num_q, c->k_pad, c->ext_limbs(level));
     return hipGetLastError();
 }

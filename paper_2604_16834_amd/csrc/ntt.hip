@@ -88,6 +88,8 @@ struct NttArgs {
     const TwPair* tw;    // [M][N]
     u32 log_n, log_lo, log_hi;
     u32 last;            // this pass writes the final result (canonical; inverse: times 1/N)
+    u32 use_src_list;    // batch item b reads src_list.p[b] instead of src + b*src_bstride*N
+    PtrList8 src_list;
 };
 
 struct PolyRef {
@@ -101,7 +103,7 @@ __device__ __forceinline__ PolyRef poly_ref(const NttArgs& A, const PolyList& pl
     const u32 p = blockIdx.y, b = p / pl.n, a = p % pl.n;
     const u32 m_idx = pl.mod[a];
     PolyRef r;
-    r.src = A.src + (((size_t)b * A.src_bstride + pl.spos[a]) << A.log_n);
+    r.src = (A.use_src_list ? A.src_list.p[b] : A.src + (((size_t)b * A.src_bstride) << A.log_n)) + ((size_t)pl.spos[a] << A.log_n);
     r.dst = A.dst + (((size_t)b * A.dst_bstride + pl.dpos[a]) << A.log_n);
     r.tw = A.tw + ((size_t)m_idx << A.log_n);
     r.mc = A.mc[m_idx];
@@ -336,8 +338,9 @@ static void launch_hi_any(u32 log_hi, bool inverse, dim3 grid, hipStream_t st, c
 }
 
 hipError_t launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, size_t src_bstride, u64* dst,
-                      size_t dst_bstride, const PolyList& pl, u32 batch, hipStream_t st) {
+                      size_t dst_bstride, const PolyList& pl, u32 batch, hipStream_t st, const u64* const* src_ptrs) {
     if (pl.n == 0 || batch == 0) return hipSuccess;
+    if (src_ptrs && batch > KS_MAX_BATCH) return hipErrorInvalidValue;
     NttArgs A;
     A.src = src;
     A.dst = dst;
@@ -349,6 +352,8 @@ hipError_t launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, size_t sr
     A.log_lo = c->log_lo;
     A.log_hi = c->log_hi;
     A.last = 1;
+    A.use_src_list = src_ptrs ? 1 : 0;
+    for (u32 b = 0; b < KS_MAX_BATCH; b++) A.src_list.p[b] = (src_ptrs && b < batch) ? src_ptrs[b] : nullptr;
     const u32 polys = pl.n * batch;
     const dim3 block(NTT_THREADS);
     const double pass_bytes = 16.0 * polys * c->N;
@@ -364,6 +369,7 @@ hipError_t launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, size_t sr
     NttArgs B = A;
     B.src = dst;
     B.src_bstride = dst_bstride;
+    B.use_src_list = 0;
     PolyList pd = pl;
     for (u32 i = 0; i < pl.n; i++) pd.spos[i] = pl.dpos[i];
     if (!inverse) {

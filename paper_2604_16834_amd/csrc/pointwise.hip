@@ -78,73 +78,78 @@ hipError_t launch_ptct_mac(const ckks_ctx* c, u32 level, const u64* const* pts, 
     return hipGetLastError();
 }
 
-// ---- rescale ------------------------------------------------------------------------------------
-// r [2][N]: dropped limb of both components in coefficient form.  w[comp][i][x] = centred r mod q_i.
+// ---- rescale (batched over ciphertext components) -----------------------------------------------
+// r [batch][N]: dropped limbs in coefficient form.  w[b][i][x] = centred r[b][x] mod q_i.
 __global__ __launch_bounds__(PW_THREADS) void rescale_conv_kernel(const u64* __restrict__ r, u64* __restrict__ w,
                                                                   const u64* __restrict__ tab, const ModConst* __restrict__ mc,
                                                                   u32 N, u32 level, u32 num_q) {
     const u32 x = blockIdx.x * PW_THREADS + threadIdx.x;
     if (x >= N) return;
-    const u32 i = blockIdx.y, comp = blockIdx.z;
+    const u32 i = blockIdx.y, b = blockIdx.z;
     const ModConst m = mc[i];
     const u64 ql = mc[level].q;
-    const u64 rv = r[(size_t)comp * N + x];
+    const u64 rv = r[(size_t)b * N + x];
     u64 v = reduce_word(rv, m);
     if (rv > ql / 2) v = sub_mod(v, tab[((size_t)level * num_q + i) * 3 + 2], m.q);  // r - q_l
-    w[((size_t)comp * level + i) * N + x] = v;
+    w[((size_t)b * level + i) * N + x] = v;
 }
 
-hipError_t launch_rescale_conv(const ckks_ctx* c, u32 level, const u64* r, u64* w, hipStream_t st) {
-    dim3 grid((c->N + PW_THREADS - 1) / PW_THREADS, level, 2);
-    { ProfScope ps__(c, K_RESCALE_CONV, st, 16.0 * c->N * (1.0 + level), 0.0); hipLaunchKernelGGL(rescale_conv_kernel, grid, dim3(PW_THREADS), 0, st, r, w, c->d_rescale, c->d_mc, c->N, level, c->num_q); }
+hipError_t launch_rescale_conv(const ckks_ctx* c, u32 level, const u64* r, u64* w, u32 batch, hipStream_t st) {
+    dim3 grid((c->N + PW_THREADS - 1) / PW_THREADS, level, batch);
+    ProfScope ps__(c, K_RESCALE_CONV, st, 8.0 * batch * c->N * (1.0 + level), 0.0);
+    hipLaunchKernelGGL(rescale_conv_kernel, grid, dim3(PW_THREADS), 0, st, r, w, c->d_rescale, c->d_mc, c->N, level, c->num_q);
     return hipGetLastError();
 }
 
-// out[comp][i] = (ct[comp][i] - w[comp][i]) * q_l^-1, i < level; ct has component stride ct_cstride
-__global__ __launch_bounds__(PW_THREADS) void rescale_final_kernel(const u64* __restrict__ ct, size_t ct_cstride,
-                                                                   const u64* __restrict__ w, u64* __restrict__ out,
-                                                                   const u64* __restrict__ tab, const ModConst* __restrict__ mc,
-                                                                   u32 N, u32 level, u32 num_q) {
+// out_b[comp][i] = (ct_b[comp][i] - w[2b+comp][i]) * q_l^-1, i < level; ct_b = ct.p[b] with component stride ct_cstride
+__global__ __launch_bounds__(PW_THREADS) void rescale_final_kernel(PtrList8 ct, size_t ct_cstride, const u64* __restrict__ w,
+                                                                   OutList8 out, const u64* __restrict__ tab,
+                                                                   const ModConst* __restrict__ mc, u32 N, u32 level, u32 num_q) {
     const u32 x = blockIdx.x * PW_THREADS + threadIdx.x;
     if (x >= N) return;
-    const u32 i = blockIdx.y, comp = blockIdx.z;
+    const u32 i = blockIdx.y, z = blockIdx.z, b = z >> 1, comp = z & 1;
     const u64 q = mc[i].q;
     const u64* t = tab + ((size_t)level * num_q + i) * 3;
-    const size_t o = ((size_t)comp * level + i) * N + x;
-    u64 d = sub_mod(ct[comp * ct_cstride + (size_t)i * N + x], w[o], q);
-    out[o] = mul_shoup(d, t[0], t[1], q);
+    u64 d = sub_mod(ct.p[b][comp * ct_cstride + (size_t)i * N + x], w[((size_t)z * level + i) * N + x], q);
+    out.p[b][((size_t)comp * level + i) * N + x] = mul_shoup(d, t[0], t[1], q);
 }
 
-hipError_t launch_rescale_final(const ckks_ctx* c, u32 level, const u64* ct, size_t ct_cstride, const u64* w, u64* out, hipStream_t st) {
-    dim3 grid((c->N + PW_THREADS - 1) / PW_THREADS, level, 2);
-    { ProfScope ps__(c, K_RESCALE_FINAL, st, 48.0 * c->N * level, 2.0 * c->N * level); hipLaunchKernelGGL(rescale_final_kernel, grid, dim3(PW_THREADS), 0, st, ct, ct_cstride, w, out, c->d_rescale, c->d_mc, c->N,
-                       level, c->num_q); }
+hipError_t launch_rescale_final(const ckks_ctx* c, u32 level, const PtrList8& ct, size_t ct_cstride, const u64* w, const OutList8& out,
+                                u32 n, hipStream_t st) {
+    dim3 grid((c->N + PW_THREADS - 1) / PW_THREADS, level, 2 * n);
+    ProfScope ps__(c, K_RESCALE_FINAL, st, 48.0 * n * c->N * level, 2.0 * n * c->N * level);
+    hipLaunchKernelGGL(rescale_final_kernel, grid, dim3(PW_THREADS), 0, st, ct, ct_cstride, w, out, c->d_rescale, c->d_mc, c->N, level,
+                       c->num_q);
     return hipGetLastError();
 }
 
-// ---- tensor product of two ciphertexts ----------------------------------------------------------
-// d0 = a0 b0, d1 = a0 b1 + a1 b0, d2 = a1 b1 on limbs 0..level; operands may sit at a higher level
-// (component strides a_cstride, b_cstride in elements)
-__global__ __launch_bounds__(PW_THREADS) void tensor_kernel(const u64* __restrict__ a, size_t a_cstride, const u64* __restrict__ b,
-                                                            size_t b_cstride, u64* __restrict__ d0, u64* __restrict__ d1,
-                                                            u64* __restrict__ d2, const ModConst* __restrict__ mc, u32 N) {
+// ---- tensor product of ciphertext pairs -----------------------------------------------------------
+// item b: d0 = a0 b0, d1 = a0 b1 + a1 b0, d2 = a1 b1 on limbs 0..level; operands a.p[b], b.p[b] may sit
+// at a higher level (component strides in elements); d0/d1/d2 are [n][level+1][N]
+__global__ __launch_bounds__(PW_THREADS) void tensor_kernel(PtrList8 a, size_t a_cstride, PtrList8 b, size_t b_cstride,
+                                                            u64* __restrict__ d0, u64* __restrict__ d1, u64* __restrict__ d2,
+                                                            const ModConst* __restrict__ mc, u32 N, u32 level) {
     const u32 x = blockIdx.x * PW_THREADS + threadIdx.x;
     if (x >= N) return;
-    const u32 i = blockIdx.y;
+    const u32 i = blockIdx.y, z = blockIdx.z;
     const ModConst m = mc[i];
     const size_t o = (size_t)i * N + x;
-    const u64 a0 = a[o], a1 = a[a_cstride + o], b0 = b[o], b1 = b[b_cstride + o];
-    d0[o] = mulmod_barrett(a0, b0, m);
+    const u64* pa = a.p[z];
+    const u64* pb = b.p[z];
+    const u64 a0 = pa[o], a1 = pa[a_cstride + o], b0 = pb[o], b1 = pb[b_cstride + o];
+    const size_t oo = ((size_t)z * (level + 1) + i) * N + x;
+    d0[oo] = mulmod_barrett(a0, b0, m);
     U128 s = mul_wide(a0, b1);
     acc_wide(s, a1, b0);
-    d1[o] = barrett_reduce(s, m);
-    d2[o] = mulmod_barrett(a1, b1, m);
+    d1[oo] = barrett_reduce(s, m);
+    d2[oo] = mulmod_barrett(a1, b1, m);
 }
 
-hipError_t launch_tensor(const ckks_ctx* c, u32 level, const u64* a, size_t a_cstride, const u64* b, size_t b_cstride, u64* d0,
-                         u64* d1, u64* d2, hipStream_t st) {
-    dim3 grid((c->N + PW_THREADS - 1) / PW_THREADS, level + 1);
-    { ProfScope ps__(c, K_TENSOR, st, 56.0 * c->N * (level + 1.0), 4.0 * c->N * (level + 1.0)); hipLaunchKernelGGL(tensor_kernel, grid, dim3(PW_THREADS), 0, st, a, a_cstride, b, b_cstride, d0, d1, d2, c->d_mc, c->N); }
+hipError_t launch_tensor(const ckks_ctx* c, u32 level, const PtrList8& a, size_t a_cstride, const PtrList8& b, size_t b_cstride,
+                         u64* d0, u64* d1, u64* d2, u32 n, hipStream_t st) {
+    dim3 grid((c->N + PW_THREADS - 1) / PW_THREADS, level + 1, n);
+    ProfScope ps__(c, K_TENSOR, st, 56.0 * n * c->N * (level + 1.0), 4.0 * n * c->N * (level + 1.0));
+    hipLaunchKernelGGL(tensor_kernel, grid, dim3(PW_THREADS), 0, st, a, a_cstride, b, b_cstride, d0, d1, d2, c->d_mc, c->N, level);
     return hipGetLastError();
 }
 
@@ -283,36 +288,40 @@ hipError_t launch_weighted_sum(const ckks_ctx* c, u32 level, const u64* xs, u32 
     return hipGetLastError();
 }
 
-// ---- out = ka * a + kb * b (+ add) on limbs 0..level, integer scalars given by residues ---------
+// ---- out_b = ka * a_b + kb * b_b (+ add_b) on limbs 0..level, integer scalars given by residues ----
 struct Scalars {
     u64 ka[CKKS_MAX_MODULI];
     u64 kb[CKKS_MAX_MODULI];
 };
 
-__global__ __launch_bounds__(PW_THREADS) void lincomb2_kernel(const u64* __restrict__ a, size_t a_cstride, const u64* __restrict__ b,
-                                                              size_t b_cstride, const u64* __restrict__ add, Scalars K,
-                                                              u64* __restrict__ out, const ModConst* __restrict__ mc, u32 N, u32 level) {
+__global__ __launch_bounds__(PW_THREADS) void lincomb2_kernel(PtrList8 a, size_t a_cstride, PtrList8 b, size_t b_cstride,
+                                                              const u64* __restrict__ add, size_t add_bstride, Scalars K,
+                                                              u64* __restrict__ out, size_t out_bstride,
+                                                              const ModConst* __restrict__ mc, u32 N, u32 level) {
     const u32 x = blockIdx.x * PW_THREADS + threadIdx.x;
     if (x >= N) return;
-    const u32 i = blockIdx.y, comp = blockIdx.z;
+    const u32 i = blockIdx.y, z = blockIdx.z, bi = z >> 1, comp = z & 1;
     const ModConst m = mc[i];
     const size_t o = (size_t)i * N + x;
-    U128 s = mul_wide(a[comp * a_cstride + o], K.ka[i]);
-    acc_wide(s, b[comp * b_cstride + o], K.kb[i]);
+    U128 s = mul_wide(a.p[bi][comp * a_cstride + o], K.ka[i]);
+    acc_wide(s, b.p[bi][comp * b_cstride + o], K.kb[i]);
     const size_t oo = ((size_t)comp * (level + 1) + i) * N + x;
     u64 r = barrett_reduce(s, m);
-    if (add) r = add_mod(r, add[oo], m.q);
-    out[oo] = r;
+    if (add) r = add_mod(r, add[bi * add_bstride + oo], m.q);
+    out[bi * out_bstride + oo] = r;
 }
 
-hipError_t launch_lincomb2(const ckks_ctx* c, u32 level, const u64* a, size_t a_cstride, const u64* ka, const u64* b,
-                           size_t b_cstride, const u64* kb, const u64* add, u64* out, hipStream_t st) {
+hipError_t launch_lincomb2(const ckks_ctx* c, u32 level, const PtrList8& a, size_t a_cstride, const u64* ka, const PtrList8& b,
+                           size_t b_cstride, const u64* kb, const u64* add, size_t add_bstride, u64* out, size_t out_bstride, u32 n,
+                           hipStream_t st) {
     Scalars K;
     for (u32 i = 0; i < CKKS_MAX_MODULI; i++) {
         K.ka[i] = i <= level ? ka[i] : 0;
         K.kb[i] = i <= level ? kb[i] : 0;
     }
-    dim3 grid((c->N + PW_THREADS - 1) / PW_THREADS, level + 1, 2);
-    { ProfScope ps__(c, K_LINCOMB2, st, 16.0 * c->N * (level + 1.0) * (3.0 + (add ? 1.0 : 0.0)), 4.0 * c->N * (level + 1.0)); hipLaunchKernelGGL(lincomb2_kernel, grid, dim3(PW_THREADS), 0, st, a, a_cstride, b, b_cstride, add, K, out, c->d_mc, c->N, level); }
+    dim3 grid((c->N + PW_THREADS - 1) / PW_THREADS, level + 1, 2 * n);
+    ProfScope ps__(c, K_LINCOMB2, st, 16.0 * n * c->N * (level + 1.0) * (3.0 + (add ? 1.0 : 0.0)), 4.0 * n * c->N * (level + 1.0));
+    hipLaunchKernelGGL(lincomb2_kernel, grid, dim3(PW_THREADS), 0, st, a, a_cstride, b, b_cstride, add, add_bstride, K, out, out_bstride,
+                       c->d_mc, c->N, level);
     return hipGetLastError();
 }

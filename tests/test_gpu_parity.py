@@ -186,23 +186,26 @@ def test_he_conv_equals_composition_of_exported_ops():
 
 
 # ------------------------------------------------------------------------------------ activation
-def test_poly_activation_matches_oracle():
+@pytest.mark.parametrize("n_ct", [1, 3, 10])
+def test_poly_activation_matches_oracle(n_ct):
+    """1 ciphertext, a partial batch, and more than one batch of 8."""
     wl = CONFIGS["small_block"]
     p = wl.params()
     orc, ctx = both(p)
     level = p.num_q - 1
     s, s_ntt = orc.gen_secret(301)
     rlk = orc.gen_relin_key(s_ntt, 302)
-    x = np.random.default_rng(303).uniform(-1, 1, orc.n)
+    rng = np.random.default_rng(303)
     scale = 2.0 ** 50
-    ct = orc.encrypt(x, scale, level, s_ntt, 304)
     plan = orc.act_schedule(level, scale)
-    want = orc.poly_activation(ct, level, plan["k"], rlk)
-    out = hx.he_poly_act_deg7(ctx, hx.from_host(ct), level, plan["k"], hx.ckks_key_load(ctx, hx.from_host(rlk), 0))
-    got = hx.to_host(out)
-    assert np.array_equal(got, want)
-    dec = orc.decrypt(got, plan["out_level"], s_ntt, plan["out_scale"])
-    assert np.abs(dec - activation_reference(x)).max() < 1e-3
+    xs = [rng.uniform(-1, 1, orc.n) for _ in range(n_ct)]
+    cts = [orc.encrypt(x, scale, level, s_ntt, 304 + i) for i, x in enumerate(xs)]
+    outs = hx.he_poly_act_deg7(ctx, [hx.from_host(ct) for ct in cts], level, plan["k"], hx.ckks_key_load(ctx, hx.from_host(rlk), 0))
+    for i in range(n_ct):
+        got = hx.to_host(outs[i])
+        assert np.array_equal(got, orc.poly_activation(cts[i], level, plan["k"], rlk)), f"channel {i}"
+        dec = orc.decrypt(got, plan["out_level"], s_ntt, plan["out_scale"])
+        assert np.abs(dec - activation_reference(xs[i])).max() < 1e-3
 
 
 # ----------------------------------------------------------------------------------- error paths
