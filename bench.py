@@ -42,6 +42,10 @@ def parse_args():
     ap.add_argument("--workload", default="cfg5_resnet20_stage3")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--no-kernel-timing", action="store_true", help="skip the per-kernel event pass")
+    ap.add_argument("--no-microbench", action="store_true", help="skip the rotation and NTT microbenchmarks")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run the library's plain copy kernel on one ciphertext (24 MiB in, 24 MiB out): the known-size "
+                         "dispatch that hardware-counter runs are scaled by")
     return ap.parse_args()
 
 
@@ -175,20 +179,60 @@ def main():
             ach = ki["bytes"] / (ki["ms"] * 1e-3) / 1e9
             result["key_inner_hbm"] = {"achieved_GBs": ach, "frac_of_peak": ach / HBM_PEAK_GBS, "avg_us": 1e3 * ki["ms"] / ki["launches"]}
 
-    # rotations/s on the rotation microbenchmark shape of this parameter set: 8 hoisted rotations of one ciphertext
-    rot_outs = [hx.empty(2, level + 1, N) for _ in range(8)]
-    rot_offs = [o for o in offs if o]
-    rot_keys = [k for k in keys if k is not None]
-    for hoisted in (True, False):
-        hx.ckks_rotate_hoisted(ctx, ins[0], level, rot_offs, rot_keys, hoisted, outs=rot_outs, ws=ws)
+    if args.calibration_copy:   # a rotation by 0 slots is a plain copy of the ciphertext
+        cal = hx.empty(2, level + 1, N)
+        for _ in range(3):
+            hx.ckks_rotate_hoisted(ctx, ins[0], level, [0], [None], True, outs=[cal], ws=ws)
         torch.cuda.synchronize()
-        reps = 8
+        result["calibration_copy_bytes_each_way"] = 2 * (level + 1) * N * 8
+    if args.no_microbench:
+        if not args.no_cpu_baseline:
+            result["cpu_baseline"] = cpu_baseline(wl, params)
+        print(json.dumps(result))
+        return
+    # ---- the two microbenchmark shapes, reported next to the headline value ------------------------
+    # rotation microbenchmark (24 limbs + 8 special primes, dnum 3): one ciphertext, 64 distinct offsets, 64 keys in
+    # 64 separate 96 MiB buffers (their contents are clones of the eight seeded keys: only the addresses matter)
+    n_rot_mb = 64
+    from workloads import rotation_offsets
+    mb_offs = rotation_offsets(n_rot_mb, N // 2)
+    base_keys = [k for k in keys if k is not None]
+    mb_keys = [hx.ckks_key_load(ctx, base_keys[i % len(base_keys)].tensor.clone(), hx.ckks_galois_element(ctx, r))
+               for i, r in enumerate(mb_offs)]
+    mb_outs = [hx.empty(2, level + 1, N) for _ in range(n_rot_mb)]
+    for hoisted in (True, False):
+        hx.ckks_rotate_hoisted(ctx, ins[0], level, mb_offs, mb_keys, hoisted, outs=mb_outs, ws=ws)
+        torch.cuda.synchronize()
+        reps = 3
         t0 = time.perf_counter()
         for _ in range(reps):
-            hx.ckks_rotate_hoisted(ctx, ins[0], level, rot_offs, rot_keys, hoisted, outs=rot_outs, ws=ws)
+            hx.ckks_rotate_hoisted(ctx, ins[0], level, mb_offs, mb_keys, hoisted, outs=mb_outs, ws=ws)
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
-        result["rotations_per_s_%s" % ("hoisted" if hoisted else "unhoisted")] = 8 * reps / dt
+        name = "hoisted" if hoisted else "unhoisted"
+        rate = n_rot_mb * reps / dt
+        result["rotations_per_s_%s" % name] = rate
+        # compulsory HBM traffic per rotation: key 96 MiB + c0 12 MiB + output 24 MiB (+ 24 MiB input when unhoisted)
+        mib = (96 + 12 + 24) if hoisted else (96 + 24 + 24)
+        result["rotation_%s_effective_GBs" % name] = rate * mib * 2**20 / 1e9
+    del mb_keys, mb_outs
+    # NTT microbenchmark: 64 polynomials x 30 limbs at N = 2^16, forward then inverse
+    p2 = CONFIGS["cfg2_ntt"].params()
+    ctx2 = hx.Context(p2)
+    polys = hx.from_host(uniform_residues((64, p2.num_q, N), p2.moduli, "cfg2"))
+    idx2 = list(range(p2.num_q))
+    hx.ckks_ntt_fwd(ctx2, polys, idx2)
+    hx.ckks_ntt_inv(ctx2, polys, idx2)
+    torch.cuda.synchronize()
+    reps = 5
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        hx.ckks_ntt_fwd(ctx2, polys, idx2)
+        hx.ckks_ntt_inv(ctx2, polys, idx2)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    result["ntt_limbs_per_s"] = 2 * 64 * p2.num_q * reps / dt          # forward and inverse limb transforms
+    result["ntt_butterflies_per_s"] = result["ntt_limbs_per_s"] * (N // 2) * p2.log_n
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, params)

@@ -1,0 +1,149 @@
+"""GPU parity at the full benchmark sizes (N = 2^16), in the launch configurations bench.py times.
+Where the CPU oracle can afford it the comparison is limb for limb; elsewhere sampled outputs are
+compared limb for limb and the rest is checked through properties that hold at any size (round
+trips, hoisted == unhoisted, decryption against float64 references)."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+if not torch.cuda.is_available():
+    pytest.skip("needs a GPU", allow_module_level=True)
+
+import paper_2604_16834_amd as hx  # noqa: E402
+from oracle import Oracle, conv2d_reference, activation_reference  # noqa: E402
+from workloads import CONFIGS, image_batch, conv_weights, conv_tap_offsets, rotation_offsets, uniform_residues  # noqa: E402
+from gpu_common import w_residues  # noqa: E402
+
+
+def test_cfg2_ntt_microbenchmark_shape():
+    """64 polynomials x 30 limbs at N = 2^16: forward checked on sampled limb-polys against the
+    oracle, inverse checked by the exact round trip on all 1920 of them."""
+    wl = CONFIGS["cfg2_ntt"]
+    p = wl.params()
+    orc, ctx = Oracle(p), hx.Context(p)
+    idx = list(range(p.num_q))
+    polys = uniform_residues((wl.ntt_batch, p.num_q, orc.N), p.moduli, "cfg2")
+    d = hx.from_host(polys)
+    orig = d.clone()
+    hx.ckks_ntt_fwd(ctx, d, idx)
+    fwd = d.clone()
+    for b, t in [(0, 0), (0, 29), (17, 5), (63, 0), (63, 29), (31, 14)]:
+        assert np.array_equal(hx.to_host(fwd[b, t]), orc.ntt_fwd(polys[b, t], t)), (b, t)
+    assert not torch.equal(fwd, orig)
+    hx.ckks_ntt_inv(ctx, d, idx)
+    assert torch.equal(d, orig)
+
+
+def test_cfg3_rotation_microbenchmark_shape():
+    """One ciphertext (24 limbs + 8 special primes, dnum 3) rotated by 64 distinct offsets with 64
+    keys: every hoisted output against the oracle, unhoisted == hoisted on the GPU, sampled
+    unhoisted outputs against the oracle, every output decrypted against the rolled slots."""
+    wl = CONFIGS["cfg3_rotations"]
+    p = wl.params()
+    orc, ctx = Oracle(p), hx.Context(p)
+    level = p.num_q - 1
+    s, s_ntt = orc.gen_secret(31)
+    z = np.random.default_rng(32).uniform(-1, 1, orc.n)
+    scale = 2.0 ** 40
+    ct = orc.encrypt(z, scale, level, s_ntt, 33)
+    offs = rotation_offsets(wl.n_rot, orc.n)
+    keys = [orc.gen_rotation_key(s, s_ntt, r, 1000 + i) for i, r in enumerate(offs)]
+    dkeys = [hx.ckks_key_load(ctx, hx.from_host(k), hx.ckks_galois_element(ctx, r)) for k, r in zip(keys, offs)]
+    d_ct = hx.from_host(ct)
+    hoisted = hx.ckks_rotate_hoisted(ctx, d_ct, level, offs, dkeys, True)
+    unhoisted = hx.ckks_rotate_hoisted(ctx, d_ct, level, offs, dkeys, False)
+    digits = orc.modup(ct[1], level)
+    for i, r in enumerate(offs):
+        got = hx.to_host(hoisted[i])
+        assert np.array_equal(got, orc.rotate(ct, level, r, keys[i], True, digits)), f"hoisted offset {r}"
+        assert torch.equal(hoisted[i], unhoisted[i]), f"unhoisted != hoisted at offset {r}"
+        assert np.abs(orc.decrypt(got, level, s_ntt, scale) - np.roll(z, -r)).max() < 1e-5
+    for i in (0, 37, 63):
+        assert np.array_equal(hx.to_host(unhoisted[i]), orc.rotate(ct, level, offs[i], keys[i], False)), f"unhoisted offset {offs[i]}"
+
+
+def _conv_inputs(wl, p, orc, level, seed, weight_gain=1.0):
+    s, s_ntt = orc.gen_secret(seed)
+    img = image_batch(wl.batch, wl.c_in, wl.height, wl.width)
+    w = conv_weights(wl.c_out, wl.c_in) * weight_gain
+    cts = [orc.encrypt(orc.pack_channel(img, c), 2.0 ** 40, level, s_ntt, seed + 10 + c) for c in range(wl.c_in)]
+    offs = conv_tap_offsets(wl.width)
+    keys = {off: orc.gen_rotation_key(s, s_ntt, off, seed + 500 + i) for i, off in enumerate(offs) if off}
+    return s, s_ntt, img, w, cts, offs, keys
+
+
+def test_cfg4_resnet20_stage1_conv():
+    """16 -> 16 channels, 3x3, 32x32 images, batch 32 (all 32768 slots), 20 limbs + 7 special primes.
+    Two output channels limb for limb against the oracle; all sixteen decrypted against the float64
+    convolution within 1e-4."""
+    wl = CONFIGS["cfg4_resnet20_stage1"]
+    p = wl.params()
+    orc, ctx = Oracle(p), hx.Context(p)
+    level = p.num_q - 1
+    s, s_ntt, img, w, cts, offs, keys = _conv_inputs(wl, p, orc, level, 4000)
+    masks, w_int = orc.conv_operands(w, wl.height, wl.width, wl.batch, level, 2.0 ** 28, p.moduli[level] / 2.0 ** 28)
+    dkeys = [hx.ckks_key_load(ctx, hx.from_host(keys[off]), hx.ckks_galois_element(ctx, off)) if off else None for off in offs]
+    outs = hx.he_conv_batched(ctx, wl.height, wl.width, wl.batch, level, [hx.from_host(c) for c in cts], dkeys,
+                              hx.from_host(masks), hx.from_host(w_residues(w_int, p.moduli, level)), wl.c_out)
+    outs = [hx.to_host(o) for o in outs]
+    ref = conv2d_reference(img, w)
+    worst = 0.0
+    for o in range(wl.c_out):
+        dec = orc.unpack_channel(orc.decrypt(outs[o], level - 1, s_ntt, 2.0 ** 40), wl.batch, wl.height, wl.width)
+        worst = max(worst, float(np.abs(dec - ref[:, o]).max()))
+    assert worst < 1e-4, worst
+    sampled = (3, 12)
+    want = orc.he_conv(cts, level, wl.width, keys, masks, w_int, out_channels=sampled)
+    for o in sampled:
+        assert np.array_equal(outs[o], want[o]), f"output channel {o}"
+
+
+def test_cfg5_resnet20_stage3_block_slice():
+    """64 -> 64 channels on 8x8 images, batch 512, 24 limbs + 8 special primes, then the degree-7
+    activation on all 64 channels: the launch configuration bench.py times.  The oracle cannot
+    afford the 512 rotations, so: every conv output decrypted against the float64 convolution (1e-4)
+    and every activation output against the float64 polynomial (1e-3); limb-for-limb parity of the
+    activation on sampled channels (computed by the oracle from the GPU's conv output), and of the
+    whole conv on an 8 -> 3 channel slice of the same shape."""
+    wl = CONFIGS["cfg5_resnet20_stage3"]
+    p = wl.params()
+    orc, ctx = Oracle(p), hx.Context(p)
+    level = p.num_q - 1
+    # weights scaled by 1/5 so that the conv output stays inside [-1, 1], where the polynomial is used
+    s, s_ntt, img, w, cts, offs, keys = _conv_inputs(wl, p, orc, level, 5000, weight_gain=0.2)
+    rlk = orc.gen_relin_key(s_ntt, 5999)
+    delta_pt = p.moduli[level] * 2.0 ** 10                 # conv output lands at scale 2^50
+    masks, w_int = orc.conv_operands(w, wl.height, wl.width, wl.batch, level, 2.0 ** 28, delta_pt / 2.0 ** 28)
+    dkeys = [hx.ckks_key_load(ctx, hx.from_host(keys[off]), hx.ckks_galois_element(ctx, off)) if off else None for off in offs]
+    d_masks = hx.from_host(masks)
+    d_cts = [hx.from_host(c) for c in cts]
+    conv = hx.he_conv_batched(ctx, wl.height, wl.width, wl.batch, level, d_cts, dkeys, d_masks,
+                              hx.from_host(w_residues(w_int, p.moduli, level)), wl.c_out)
+    scale = 2.0 ** 50
+    plan = orc.act_schedule(level - 1, scale)
+    d_rlk = hx.ckks_key_load(ctx, hx.from_host(rlk), 0)
+    act = hx.he_poly_act_deg7(ctx, conv, level - 1, plan["k"], d_rlk)
+    ref = conv2d_reference(img, w)
+    ref_max = float(np.abs(ref).max())
+    assert ref_max < 1.0, ref_max
+    worst_conv = worst_act = 0.0
+    for o in range(wl.c_out):
+        dec = orc.unpack_channel(orc.decrypt(hx.to_host(conv[o]), level - 1, s_ntt, scale), wl.batch, wl.height, wl.width)
+        worst_conv = max(worst_conv, float(np.abs(dec - ref[:, o]).max()))
+        dec = orc.unpack_channel(orc.decrypt(hx.to_host(act[o]), plan["out_level"], s_ntt, plan["out_scale"]), wl.batch, wl.height, wl.width)
+        worst_act = max(worst_act, float(np.abs(dec - activation_reference(ref[:, o])).max()))
+    assert worst_conv < 1e-4, worst_conv
+    assert worst_act < 1e-3, worst_act
+    for o in (0, 41):
+        want = orc.poly_activation(hx.to_host(conv[o]), level - 1, plan["k"], rlk)
+        assert np.array_equal(hx.to_host(act[o]), want), f"activation of channel {o}"
+    # an 8 -> 3 channel slice of the same layer, limb for limb
+    sub_in, sub_out = list(range(8)), [5, 20, 63]
+    w_sub = w_int[np.ix_(sub_out, sub_in)]
+    got = hx.he_conv_batched(ctx, wl.height, wl.width, wl.batch, level, [d_cts[c] for c in sub_in], dkeys, d_masks,
+                             hx.from_host(w_residues(w_sub, p.moduli, level)), len(sub_out))
+    want = orc.he_conv([cts[c] for c in sub_in], level, wl.width, keys, masks, w_sub)
+    for i in range(len(sub_out)):
+        assert np.array_equal(hx.to_host(got[i]), want[i]), f"slice output {i}"
