@@ -180,6 +180,29 @@ __global__ __launch_bounds__(KS_THREADS) void key_inner_multi_kernel(const u64* 
     const u32 t = e <= level ? e : num_q + (e - level - 1);
     const u32 xs = g == 1 ? x : galois_gather_index(x, g, log_n);
     const ModConst m = mc[t];
+    if (beta <= 4) {
+        // the thread's key words stay in registers for the whole batch
+        u64 k0[4], k1[4];
+#pragma unroll
+        for (u32 j = 0; j < 4; j++) {
+            k0[j] = j < beta ? key[(((size_t)j * 2 + 0) * M + t) * N + x] : 0;
+            k1[j] = j < beta ? key[(((size_t)j * 2 + 1) * M + t) * N + x] : 0;
+        }
+        for (u32 b = 0; b < n; b++) {
+            const u64* d = digits + b * digits_bstride;
+            U128 acc0 = {0, 0}, acc1 = {0, 0};
+#pragma unroll
+            for (u32 j = 0; j < 4; j++) {
+                const u64 dv = j < beta ? d[((size_t)j * E + e) * N + xs] : 0;
+                acc_wide(acc0, dv, k0[j]);
+                acc_wide(acc1, dv, k1[j]);
+            }
+            u64* vb = v + b * v_bstride;
+            vb[((size_t)0 * E + e) * N + x] = barrett_reduce(acc0, m);
+            vb[((size_t)1 * E + e) * N + x] = barrett_reduce(acc1, m);
+        }
+        return;
+    }
     for (u32 b = 0; b < n; b++) {
         const u64* d = digits + b * digits_bstride;
         U128 acc0 = {0, 0}, acc1 = {0, 0};

@@ -15,8 +15,8 @@
 // Twiddles psi^bitrev(i) sit in one table per modulus, each with its Shoup companion in the same
 // 16-byte word; the index of the twiddle of a butterfly group obeys T(next stage) = 2*T + bit, so a
 // thread needs only the index of its group at the first stage of a round.
-// Butterflies are Harvey's lazy ones: forward values stay in [0, 4q), inverse values in [0, 2q);
-// the last pass stores canonical residues.  Rings below 2^11 use a plain one-tile kernel.
+// Butterflies are lazy: forward values are never corrected on the way (they stay below 35q < 2^64),
+// inverse values are kept in [0, 2q); the last pass stores canonical residues.  Rings below 2^11 use a plain one-tile kernel.
 #include "ctx.h"
 
 #define NTT_THREADS 256
@@ -24,11 +24,12 @@
 #define LDS_PAD(p) ((p) + ((p) >> 3))        // keeps all three exchange patterns (almost) conflict-free
 #define LDS_PADDED_WORDS (NTT_TILE + NTT_TILE / 8)
 
+// Forward butterfly with no correction at all: the Shoup product t is in [0, 2q) for ANY 64-bit y, so
+// both outputs stay non-negative and grow by at most 2q per stage: below (1 + 2*17) q < 2^64 for every
+// supported modulus (q < 2^58) over a whole transform.  One word reduction at the very end.
 __device__ __forceinline__ void fwd_bf(u64& x, u64& y, const TwPair w, u64 q) {
-    const u64 two_q = 2 * q;
-    if (x >= two_q) x -= two_q;
     const u64 t = mul_shoup_lazy(y, w.w, w.s, q);
-    y = x + two_q - t;
+    y = x + 2 * q - t;
     x = x + t;
 }
 
@@ -41,11 +42,6 @@ __device__ __forceinline__ void inv_bf(u64& x, u64& y, const TwPair w, u64 q) {
     y = mul_shoup_lazy(d, w.w, w.s, q);
 }
 
-__device__ __forceinline__ u64 canon4(u64 v, u64 q) {  // [0,4q) -> [0,q)
-    if (v >= 2 * q) v -= 2 * q;
-    if (v >= q) v -= q;
-    return v;
-}
 
 // S radix-2 stages on 2^S "rows" of KC independent columns held in registers, v[row*KC + col];
 // row bit S-1 is the largest distance.  T = twiddle index of this group at the first stage.
@@ -88,9 +84,29 @@ struct NttArgs {
     const TwPair* tw;    // [M][N]
     u32 log_n, log_lo, log_hi;
     u32 last;            // this pass writes the final result (canonical; inverse: times 1/N)
+    u32 batch;           // batch items (each pl.n limb-polys)
+    u32 lo_group;        // slices per group of the lo-pass numbering (0: plain)
     u32 use_src_list;    // batch item b reads src_list.p[b] instead of src + b*src_bstride*N
     PtrList8 src_list;
 };
+
+// Lo-pass workgroups are numbered in groups of `grp` consecutive (limb, block) slices, batch item by
+// batch item: the `batch` tiles that use the same twiddle slice get ids that are a multiple of 8
+// apart (same XCD) and close in time, so the slice comes from HBM once and from that XCD's L2 for the
+// rest of the batch, while each batch item's `grp` tiles are one contiguous run of memory.
+struct LoTile {
+    u32 b, a, blk;
+};
+// grid = (grp, batch, slices / grp): linear id = x + grp * (y + batch * z), slice t = z * grp + x, item b = y
+// (plain numbering when grp == 0: grid = (batch, slices), b = x, t = y)
+__device__ __forceinline__ LoTile lo_tile(u32 log_hi, u32 grp) {
+    const u32 t = grp ? blockIdx.z * grp + blockIdx.x : blockIdx.y;
+    LoTile r;
+    r.b = grp ? blockIdx.y : blockIdx.x;
+    r.a = t >> log_hi;
+    r.blk = t & ((1u << log_hi) - 1);
+    return r;
+}
 
 struct PolyRef {
     const u64* src;
@@ -99,8 +115,7 @@ struct PolyRef {
     ModConst mc;
 };
 
-__device__ __forceinline__ PolyRef poly_ref(const NttArgs& A, const PolyList& pl) {
-    const u32 p = blockIdx.y, b = p / pl.n, a = p % pl.n;
+__device__ __forceinline__ PolyRef poly_ref(const NttArgs& A, const PolyList& pl, u32 b, u32 a) {
     const u32 m_idx = pl.mod[a];
     PolyRef r;
     r.src = (A.use_src_list ? A.src_list.p[b] : A.src + (((size_t)b * A.src_bstride) << A.log_n)) + ((size_t)pl.spos[a] << A.log_n);
@@ -119,8 +134,10 @@ __device__ __forceinline__ PolyRef poly_ref(const NttArgs& A, const PolyList& pl
 __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_kernel(NttArgs A, PolyList pl) {
     __shared__ u64 buf0[LDS_PADDED_WORDS];
     __shared__ u64 buf1[LDS_PADDED_WORDS];
-    const u32 tid = threadIdx.x, blk = blockIdx.x;
-    const PolyRef P = poly_ref(A, pl);
+    const u32 tid = threadIdx.x;
+    const LoTile tile = lo_tile(A.log_hi, A.lo_group);
+    const u32 blk = tile.blk;
+    const PolyRef P = poly_ref(A, pl, tile.b, tile.a);
     const u64 q = P.mc.q;
     const u64* src = P.src + ((size_t)blk << 11);
     u64* dst = P.dst + ((size_t)blk << 11);
@@ -151,14 +168,16 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_kernel(NttArgs A, Poly
     fwd_rows<2, 1>(v + 4, P.tw, 512 * TA + 2 * tid + 1, q);
     ulonglong2* out = reinterpret_cast<ulonglong2*>(dst + 8 * tid);
 #pragma unroll
-    for (int j = 0; j < 4; j++) out[j] = make_ulonglong2(canon4(v[2 * j], q), canon4(v[2 * j + 1], q));
+    for (int j = 0; j < 4; j++) out[j] = make_ulonglong2(reduce_word(v[2 * j], P.mc), reduce_word(v[2 * j + 1], P.mc));
 }
 
 __global__ __launch_bounds__(NTT_THREADS) void ntt_inv_lo_kernel(NttArgs A, PolyList pl) {
     __shared__ u64 buf0[LDS_PADDED_WORDS];
     __shared__ u64 buf1[LDS_PADDED_WORDS];
-    const u32 tid = threadIdx.x, blk = blockIdx.x;
-    const PolyRef P = poly_ref(A, pl);
+    const u32 tid = threadIdx.x;
+    const LoTile tile = lo_tile(A.log_hi, A.lo_group);
+    const u32 blk = tile.blk;
+    const PolyRef P = poly_ref(A, pl, tile.b, tile.a);
     const u64 q = P.mc.q;
     const u64* src = P.src + ((size_t)blk << 11);
     u64* dst = P.dst + ((size_t)blk << 11);
@@ -210,7 +229,7 @@ template <int LOG_HI>
 __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_hi_kernel(NttArgs A, PolyList pl) {
     constexpr int R = 1 << LOG_HI, CC = NTT_TILE / R;
     const u32 tid = threadIdx.x;
-    const PolyRef P = poly_ref(A, pl);
+    const PolyRef P = poly_ref(A, pl, blockIdx.y / pl.n, blockIdx.y % pl.n);
     const u64 q = P.mc.q;
     const u64* src = P.src + (size_t)blockIdx.x * CC;
     u64* dst = P.dst + (size_t)blockIdx.x * CC;
@@ -253,7 +272,7 @@ template <int LOG_HI>
 __global__ __launch_bounds__(NTT_THREADS) void ntt_inv_hi_kernel(NttArgs A, PolyList pl) {
     constexpr int R = 1 << LOG_HI, CC = NTT_TILE / R;
     const u32 tid = threadIdx.x;
-    const PolyRef P = poly_ref(A, pl);
+    const PolyRef P = poly_ref(A, pl, blockIdx.y / pl.n, blockIdx.y % pl.n);
     const u64 q = P.mc.q;
     u64* dst = P.dst + (size_t)blockIdx.x * CC;  // the lo pass has already moved the data to dst
     u64 v[8];
@@ -298,7 +317,7 @@ template <bool INVERSE>
 __global__ __launch_bounds__(NTT_THREADS) void ntt_small_kernel(NttArgs A, PolyList pl) {
     __shared__ u64 lds[NTT_TILE];
     const u32 tid = threadIdx.x;
-    const PolyRef P = poly_ref(A, pl);
+    const PolyRef P = poly_ref(A, pl, blockIdx.y / pl.n, blockIdx.y % pl.n);
     const u64 q = P.mc.q;
     const u32 n = 1u << A.log_n;
     for (u32 e = tid; e < n; e += NTT_THREADS) lds[e] = P.src[e];
@@ -317,7 +336,7 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_small_kernel(NttArgs A, PolyL
         __syncthreads();
     }
     for (u32 e = tid; e < n; e += NTT_THREADS)
-        P.dst[e] = INVERSE ? mul_shoup(lds[e], P.mc.n_inv, P.mc.n_inv_sh, q) : canon4(lds[e], q);
+        P.dst[e] = INVERSE ? mul_shoup(lds[e], P.mc.n_inv, P.mc.n_inv_sh, q) : reduce_word(lds[e], P.mc);
 }
 
 template <int LOG_HI>
@@ -352,6 +371,13 @@ hipError_t launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, size_t sr
     A.log_lo = c->log_lo;
     A.log_hi = c->log_hi;
     A.last = 1;
+    A.batch = batch;
+    {
+        const u32 slices = pl.n << c->log_hi;
+        A.lo_group = 0;
+        for (u32 g = 64; g >= 8; g >>= 1)
+            if (slices % g == 0) { A.lo_group = g; break; }
+    }
     A.use_src_list = src_ptrs ? 1 : 0;
     for (u32 b = 0; b < KS_MAX_BATCH; b++) A.src_list.p[b] = (src_ptrs && b < batch) ? src_ptrs[b] : nullptr;
     const u32 polys = pl.n * batch;
@@ -363,7 +389,9 @@ hipError_t launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, size_t sr
         else hipLaunchKernelGGL(ntt_small_kernel<false>, dim3(1, polys), block, 0, st, A, pl);
         return hipGetLastError();
     }
-    const dim3 grid(c->N >> CKKS_TILE_LOG, polys);  // both passes: one workgroup per 2^11 points
+    const dim3 grid(c->N >> CKKS_TILE_LOG, polys);  // hi pass: one workgroup per 2^11 points
+    const u32 slices = pl.n << c->log_hi;
+    const dim3 grid_lo = A.lo_group ? dim3(A.lo_group, batch, slices / A.lo_group) : dim3(batch, slices);  // see lo_tile()
     const double lo_ops = 0.5 * polys * c->N * c->log_lo, hi_ops = 0.5 * polys * c->N * c->log_hi;
     // the second pass of either direction continues in place on dst
     NttArgs B = A;
@@ -375,14 +403,14 @@ hipError_t launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, size_t sr
     if (!inverse) {
         if (c->log_hi > 0) {
             { ProfScope ps__(c, K_NTT_FWD_HI, st, pass_bytes, hi_ops); launch_hi_any(c->log_hi, false, grid, st, A, pl); }
-            { ProfScope ps__(c, K_NTT_FWD_LO, st, pass_bytes, lo_ops); hipLaunchKernelGGL(ntt_fwd_lo_kernel, grid, block, 0, st, B, pd); }
+            { ProfScope ps__(c, K_NTT_FWD_LO, st, pass_bytes, lo_ops); hipLaunchKernelGGL(ntt_fwd_lo_kernel, grid_lo, block, 0, st, B, pd); }
         } else {
             ProfScope ps__(c, K_NTT_FWD_LO, st, pass_bytes, lo_ops);
-            hipLaunchKernelGGL(ntt_fwd_lo_kernel, grid, block, 0, st, A, pl);
+            hipLaunchKernelGGL(ntt_fwd_lo_kernel, grid_lo, block, 0, st, A, pl);
         }
     } else {
         A.last = c->log_hi == 0;
-        { ProfScope ps__(c, K_NTT_INV_LO, st, pass_bytes, lo_ops); hipLaunchKernelGGL(ntt_inv_lo_kernel, grid, block, 0, st, A, pl); }
+        { ProfScope ps__(c, K_NTT_INV_LO, st, pass_bytes, lo_ops); hipLaunchKernelGGL(ntt_inv_lo_kernel, grid_lo, block, 0, st, A, pl); }
         if (c->log_hi > 0) { ProfScope ps__(c, K_NTT_INV_HI, st, pass_bytes, hi_ops); launch_hi_any(c->log_hi, true, grid, st, B, pd); }
     }
     return hipGetLastError();
