@@ -28,7 +28,7 @@ __device__ __forceinline__ u32 galois_gather_index(u32 k, u32 g, u32 log_n) {
 // y     [nd][N]      digit limbs in coefficient form (canonical)
 // c_in  [level+1][N] the polynomial being switched, NTT form (source of the digit's own limbs)
 // digit [E][N]       out: own limbs copied (NTT form), other limbs in coefficient form
-#define MODUP_LIMBS_PER_BLOCK 4
+#define MODUP_LIMBS_PER_BLOCK 16
 __global__ __launch_bounds__(KS_THREADS) void modup_conv_kernel(const u64* __restrict__ y, size_t y_bstride, PtrList8 c_list,
                                                                 u64* __restrict__ digit, size_t digit_bstride,
                                                                 const u64* __restrict__ tab, const ModConst* __restrict__ mc, u32 N,
@@ -233,7 +233,7 @@ hipError_t launch_key_inner_multi(const ckks_ctx* c, u32 level, const u64* digit
 
 // ---- ModDown, conversion of the P-part ----------------------------------------------------------
 // v [2][E][N]: limbs level+1.. hold the P-part in coefficient form.  w [2][level+1][N] (coefficients)
-#define MODDOWN_LIMBS_PER_BLOCK 4
+#define MODDOWN_LIMBS_PER_BLOCK 12
 __global__ __launch_bounds__(KS_THREADS) void moddown_conv_kernel(const u64* __restrict__ v, u64* __restrict__ w,
                                                                   const u64* __restrict__ tab, const ModConst* __restrict__ mc,
                                                                   u32 N, u32 level, u32 num_q, u32 k, u32 kp, u32 E) {
