@@ -146,12 +146,21 @@ int ckks_ctct_mul_relin(const ckks_ctx* ctx, const uint64_t* d_a, const uint64_t
  *   pt[o,c,tap] = w_int[o,c,tap] * M_tap  (mod q_i),
  * M_tap = d_tap_masks[tap] the encoded 0/1 validity mask of the tap (uint64[9][level+1][N], NTT
  * form) and w_int the integer weight, given by its residues d_w_res uint64[C_out][C_in][9][level+1].
- * rot_keys[tap] is the key of offset dy*W+dx (entry 4, the centre, is ignored).  The eight
- * rotations of each input share one decomposition (hoisted).
+ * rot_keys[tap] is the key of offset dy*W+dx (entry 4, the centre, is ignored).  With
+ * HE_CONV_ALIGN_DIRECT the eight rotations of each input share one decomposition (hoisted).
  * h_d_in: C_in device pointers uint64[2][level+1][N]; h_d_out: C_out device pointers
  * uint64[2][level][N].  Fails with CKKS_ERR_INVALID_ARG if H*W*batch > N/2 (Eq. 4). */
+typedef enum he_conv_alignment {
+    HE_CONV_ALIGN_DIRECT = 0,   /* eight rotations of the input by dy*W+dx, eight keys, one decomposition */
+    HE_CONV_ALIGN_FOUR_KEYS = 1 /* the paper's input alignment (Eqs. 8-10): C^-1 = Rot(in,-1), C^+1 =
+                                   Rot(in,+1), then Rot(.,-W) and Rot(.,+W) of C^-1, in, C^+1; only the keys
+                                   of -1, +1, -W, +W (rot_keys entries 3, 5, 1, 7) are read; three
+                                   decompositions per input; half the resident key bytes */
+} he_conv_alignment;
+
 typedef struct he_conv_desc {
     uint32_t c_in, c_out, height, width, batch, level;
+    uint32_t alignment; /* he_conv_alignment; both give the same slots up to noise, different residues */
 } he_conv_desc;
 
 /* Workspace bytes he_conv_batched needs for this shape (0 on invalid arguments): the shared

@@ -413,24 +413,42 @@ class Oracle:
         w_int = round_half_away(np.asarray(weights, dtype=np.float64).reshape(weights.shape[0], weights.shape[1], 9) * delta_w).astype(np.int64)
         return M, w_int
 
+    def align_direct(self, ct, level: int, width: int, rot_keys: Dict[int, np.ndarray], hoisted: bool = True) -> List[np.ndarray]:
+        """The nine aligned copies of one channel ciphertext, tap (dy,dx) in row-major order, each by
+        its own rotation Rot(ct, dy*W+dx): eight keys, one shared decomposition when hoisted."""
+        ct = _u64(ct)
+        digits = self.modup(ct[1], level) if hoisted else None
+        row = []
+        for dy in (-1, 0, 1):
+            for dx in (-1, 0, 1):
+                off = dy * width + dx
+                row.append(ct if off == 0 else self.rotate(ct, level, off, rot_keys[off], hoisted, digits))
+        return row
+
+    def align_four_keys(self, ct, level: int, width: int, rot_keys: Dict[int, np.ndarray]) -> List[np.ndarray]:
+        """The paper's input alignment (Eqs. 8-10) with the four keys {-1, +1, -W, +W}:
+        C^-1 = Rot(ct, -1), C^+1 = Rot(ct, +1), then Rot(., -W) and Rot(., +W) of C^-1, ct, C^+1.
+        Returned in the order of Eq. 10, which is the row-major tap order."""
+        ct = _u64(ct)
+        W = width
+        d0 = self.modup(ct[1], level)                       # ct is rotated four times: one decomposition
+        cm = self.rotate(ct, level, -1, rot_keys[-1], True, d0)
+        cp = self.rotate(ct, level, +1, rot_keys[+1], True, d0)
+        dm, dp = self.modup(cm[1], level), self.modup(cp[1], level)
+        up = [self.rotate(b, level, -W, rot_keys[-W], True, d) for b, d in ((cm, dm), (ct, d0), (cp, dp))]
+        down = [self.rotate(b, level, +W, rot_keys[+W], True, d) for b, d in ((cm, dm), (ct, d0), (cp, dp))]
+        return up + [cm, ct, cp] + down
+
     def he_conv(self, cts: Sequence[np.ndarray], level: int, width: int, rot_keys: Dict[int, np.ndarray],
                 M: np.ndarray, w_int: np.ndarray, out_channels: Optional[Iterable[int]] = None,
-                hoisted: bool = True) -> Dict[int, np.ndarray]:
+                hoisted: bool = True, four_keys: bool = False) -> Dict[int, np.ndarray]:
         """Batched 3x3 convolution layer on channel-packed ciphertexts:
-        out_o = Rescale( sum_c sum_tap pt[o,c,tap] (.) Rot(ct_c, dy*W+dx) )   (Eqs. 10-11).
+        out_o = Rescale( sum_c sum_tap pt[o,c,tap] (.) R_tap(ct_c) )   (Eqs. 10-11),
+        R_tap by eight direct rotations, or by the paper's four-key two-stage alignment.
         rot_keys maps the slot offset to its rotation key.  Returns {o: ct at level-1}."""
         C_in = len(cts)
-        offsets = [dy * width + dx for dy in (-1, 0, 1) for dx in (-1, 0, 1)]
-        aligned: List[List[np.ndarray]] = []
-        for c in range(C_in):
-            digits = self.modup(_u64(cts[c])[1], level) if hoisted else None
-            row = []
-            for off in offsets:
-                if off == 0:
-                    row.append(_u64(cts[c]))
-                else:
-                    row.append(self.rotate(cts[c], level, off, rot_keys[off], hoisted, digits))
-            aligned.append(row)
+        aligned = [self.align_four_keys(cts[c], level, width, rot_keys) if four_keys
+                   else self.align_direct(cts[c], level, width, rot_keys, hoisted) for c in range(C_in)]
         outs = {}
         chans = range(w_int.shape[0]) if out_channels is None else out_channels
         for o in chans:

@@ -56,7 +56,7 @@ class _Params(C.Structure):
 
 class _ConvDesc(C.Structure):
     _fields_ = [("c_in", C.c_uint32), ("c_out", C.c_uint32), ("height", C.c_uint32), ("width", C.c_uint32),
-                ("batch", C.c_uint32), ("level", C.c_uint32)]
+                ("batch", C.c_uint32), ("level", C.c_uint32), ("alignment", C.c_uint32)]
 
 
 def _bind(path: str):
@@ -294,15 +294,18 @@ def ckks_ctct_mul_relin(ctx: Context, a: torch.Tensor, b: torch.Tensor, level: i
     return out
 
 
-def he_conv_workspace_bytes(ctx: Context, c_in: int, c_out: int, height: int, width: int, batch: int, level: int) -> int:
-    d = _ConvDesc(c_in, c_out, height, width, batch, level)
+def he_conv_workspace_bytes(ctx: Context, c_in: int, c_out: int, height: int, width: int, batch: int, level: int,
+                            four_keys: bool = False) -> int:
+    d = _ConvDesc(c_in, c_out, height, width, batch, level, int(bool(four_keys)))
     return int(_lib.he_conv_workspace_bytes(ctx.handle, C.byref(d)))
 
 
 def he_conv_batched(ctx: Context, height: int, width: int, batch: int, level: int, ins: Sequence[torch.Tensor],
                     rot_keys: Sequence[Optional[Key]], tap_masks: torch.Tensor, w_res: torch.Tensor, c_out: int,
-                    outs: Optional[List[torch.Tensor]] = None, ws: Optional[torch.Tensor] = None, stream=None) -> List[torch.Tensor]:
-    """ins: C_in tensors [2][level+1][N]; rot_keys: nine entries in tap order (centre ignored);
+                    outs: Optional[List[torch.Tensor]] = None, ws: Optional[torch.Tensor] = None, stream=None,
+                    four_keys: bool = False) -> List[torch.Tensor]:
+    """four_keys: the paper's four-key two-stage input alignment instead of eight direct rotations.
+    ins: C_in tensors [2][level+1][N]; rot_keys: nine entries in tap order (centre ignored);
     tap_masks [9][level+1][N]; w_res [C_out][C_in][9][level+1] residues of the integer weights."""
     c_in = len(ins)
     L1 = level + 1
@@ -318,8 +321,8 @@ def he_conv_batched(ctx: Context, height: int, width: int, batch: int, level: in
     for o in outs:
         if o.numel() != 2 * level * ctx.N:
             raise ValueError("each output must be [2][level][N]")
-    d = _ConvDesc(c_in, c_out, height, width, batch, level)
-    ws = _ws(ctx, ws, he_conv_workspace_bytes(ctx, c_in, c_out, height, width, batch, level))
+    d = _ConvDesc(c_in, c_out, height, width, batch, level, int(bool(four_keys)))
+    ws = _ws(ctx, ws, he_conv_workspace_bytes(ctx, c_in, c_out, height, width, batch, level, four_keys))
     ia = _ptr_array([_ptr(t) for t in ins])
     ka = _ptr_array([k.handle.value if k is not None else None for k in rot_keys])
     oa = _ptr_array([_ptr(o) for o in outs])

@@ -197,7 +197,8 @@ size_t he_conv_workspace_bytes(const ckks_ctx* c, const he_conv_desc* d) {
     if (!c || !d || !c->dnum || !level_ok(c, d->level) || d->level < 1) return 0;
     const size_t N = c->N, L1 = d->level + 1;
     return ws_ks(c, d->level, CT_BATCH, CT_BATCH) + blk((size_t)d->c_in * 9 * 2 * L1 * N) + blk((size_t)d->c_out * 2 * L1 * N) +
-           blk(weighted_sum_scratch_elems(c, d->level, d->c_in * 9, d->c_out)) + ws_rescale(c, d->level, CT_BATCH);
+           blk(weighted_sum_scratch_elems(c, d->level, d->c_in * 9, d->c_out)) + ws_rescale(c, d->level, CT_BATCH) +
+           (d->alignment == HE_CONV_ALIGN_FOUR_KEYS ? 2 * blk((size_t)CT_BATCH * 2 * L1 * N) : 0);
 }
 
 uint32_t ckks_galois_element(const ckks_ctx* c, int32_t offset) {
@@ -396,6 +397,9 @@ int he_conv_batched(const ckks_ctx* c, const he_conv_desc* d, const uint64_t* co
         return set_err(c, CKKS_ERR_INVALID_ARG, "empty convolution shape");
     if (!level_ok(c, d->level) || d->level < 1) return set_err(c, CKKS_ERR_LEVEL_MISMATCH, "convolution needs 1 <= level < num_q");
     if ((u64)d->height * d->width * d->batch > c->N / 2) return set_err(c, CKKS_ERR_INVALID_ARG, "H*W*batch exceeds the N/2 slots");
+    if (d->alignment != HE_CONV_ALIGN_DIRECT && d->alignment != HE_CONV_ALIGN_FOUR_KEYS)
+        return set_err(c, CKKS_ERR_INVALID_ARG, "unknown alignment");
+    const bool four = d->alignment == HE_CONV_ALIGN_FOUR_KEYS;
     const u32 level = d->level;
     const size_t N = c->N, L1 = level + 1, ct_elems = 2 * L1 * N;
     u32 gs[9];
@@ -405,6 +409,7 @@ int he_conv_batched(const ckks_ctx* c, const he_conv_desc* d, const uint64_t* co
             for (int dx = -1; dx <= 1; dx++, t++) {
                 gs[t] = ckks_galois_element(c, dy * (int32_t)d->width + dx);
                 if (gs[t] == 1) continue;
+                if (four && (t & 1) == 0) continue;  // the corner taps are reached in two steps: no key of their own
                 if (!rot_keys[t]) return set_err(c, CKKS_ERR_NO_KEY, "rotation key missing for a tap");
                 if (rot_keys[t]->galois_elt != gs[t]) return set_err(c, CKKS_ERR_NO_KEY, "rotation key does not match its tap offset");
             }
@@ -418,6 +423,11 @@ int he_conv_batched(const ckks_ctx* c, const he_conv_desc* d, const uint64_t* co
     u64* xs = ar.take((size_t)d->c_in * 9 * ct_elems);
     u64* acc = ar.take((size_t)d->c_out * ct_elems);
     u64* wscratch = ar.take(weighted_sum_scratch_elems(c, level, d->c_in * 9, d->c_out));
+    u64* side[2] = {nullptr, nullptr};  // C^-1 and C^+1 of the current batch (four-key alignment)
+    if (four) {
+        side[0] = ar.take((size_t)CT_BATCH * ct_elems);
+        side[1] = ar.take((size_t)CT_BATCH * ct_elems);
+    }
     if (!ok || !ar.ok() || ar.used + ws_rescale(c, level, CT_BATCH) > ar.cap)
         return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for the convolution");
     hipStream_t st = (hipStream_t)stream;
@@ -425,24 +435,71 @@ int he_conv_batched(const ckks_ctx* c, const he_conv_desc* d, const uint64_t* co
     // input alignment: nine aligned copies of every input channel, each times its tap mask.  Channels
     // go in batches: one shared pass of the decomposition kernels, then per tap one inner product that
     // streams the tap's key once for the whole batch and one batched ModDown.
+    auto mask_of = [&](u32 t) { return (const u64*)d_tap_masks + (size_t)t * L1 * N; };
+    auto slot = [&](u32 ch, u32 t) { return xs + ((size_t)ch * 9 + t) * ct_elems; };
+    // rotate the batch `base` (digits already in ws) by the offset of tap `kt`; outs[b] gets mask `m`
+    auto rotate_batch = [&](const u64* const* base, u32 n, u32 kt, u64* const* outs, const u64* m) -> int {
+        HIP_TRY(launch_key_inner_multi(c, level, ws.digits, ws.dig_b, rot_keys[kt]->d_key, gs[kt], ws.v, ws.v_b, n, st));
+        FinalItem items[CT_BATCH];
+        for (u32 b = 0; b < n; b++) items[b] = FinalItem{base[b], nullptr, m, outs[b], gs[kt], 0};
+        return run_moddown(c, level, ws, n, items, st);
+    };
     for (u32 c0 = 0; c0 < d->c_in; c0 += CT_BATCH) {
         const u32 n = d->c_in - c0 < CT_BATCH ? d->c_in - c0 : CT_BATCH;
-        const u64* c1s[CT_BATCH];
-        for (u32 b = 0; b < n; b++) c1s[b] = (const u64*)h_d_in[c0 + b] + L1 * N;
+        const u64 *in[CT_BATCH], *c1s[CT_BATCH];
+        u64* outs[CT_BATCH];
+        for (u32 b = 0; b < n; b++) {
+            in[b] = (const u64*)h_d_in[c0 + b];
+            c1s[b] = in[b] + L1 * N;
+        }
         int rc = run_modup(c, level, c1s, n, ws, st);
         if (rc) return rc;
-        for (u32 t = 0; t < 9; t++) {
-            const u64* mask = (const u64*)d_tap_masks + (size_t)t * L1 * N;
-            if (gs[t] == 1) {
-                for (u32 b = 0; b < n; b++)
-                    HIP_TRY(launch_mask_mul(c, level, mask, (const u64*)h_d_in[c0 + b], xs + ((size_t)(c0 + b) * 9 + t) * ct_elems, st));
-                continue;
+        if (!four) {
+            for (u32 t = 0; t < 9; t++) {
+                if (gs[t] == 1) {
+                    for (u32 b = 0; b < n; b++) HIP_TRY(launch_mask_mul(c, level, mask_of(t), in[b], slot(c0 + b, t), st));
+                    continue;
+                }
+                for (u32 b = 0; b < n; b++) outs[b] = slot(c0 + b, t);
+                if ((rc = rotate_batch(in, n, t, outs, mask_of(t)))) return rc;
             }
-            HIP_TRY(launch_key_inner_multi(c, level, ws.digits, ws.dig_b, rot_keys[t]->d_key, gs[t], ws.v, ws.v_b, n, st));
-            FinalItem items[CT_BATCH];
-            for (u32 b = 0; b < n; b++)
-                items[b] = FinalItem{(const u64*)h_d_in[c0 + b], nullptr, mask, xs + ((size_t)(c0 + b) * 9 + t) * ct_elems, gs[t], 0};
-            if ((rc = run_moddown(c, level, ws, n, items, st))) return rc;
+            continue;
+        }
+        // four-key alignment, first stage: the input rotated by -1, +1 (kept unmasked for the second
+        // stage) and by -W, +W (final), all from the one decomposition of the input
+        for (u32 sd = 0; sd < 2; sd++) {
+            const u32 kt = sd == 0 ? 3 : 5;
+            for (u32 b = 0; b < n; b++) outs[b] = side[sd] + (size_t)b * ct_elems;
+            if (gs[kt] == 1) {
+                for (u32 b = 0; b < n; b++) HIP_TRY(launch_copy(in[b], outs[b], ct_elems, st));
+            } else if ((rc = rotate_batch(in, n, kt, outs, nullptr))) return rc;
+        }
+        for (u32 kt = 1; kt <= 7; kt += 6) {
+            for (u32 b = 0; b < n; b++) outs[b] = slot(c0 + b, kt);
+            if (gs[kt] == 1) {
+                for (u32 b = 0; b < n; b++) HIP_TRY(launch_mask_mul(c, level, mask_of(kt), in[b], outs[b], st));
+            } else if ((rc = rotate_batch(in, n, kt, outs, mask_of(kt)))) return rc;
+        }
+        for (u32 b = 0; b < n; b++) {
+            HIP_TRY(launch_mask_mul(c, level, mask_of(4), in[b], slot(c0 + b, 4), st));
+            HIP_TRY(launch_mask_mul(c, level, mask_of(3), side[0] + (size_t)b * ct_elems, slot(c0 + b, 3), st));
+            HIP_TRY(launch_mask_mul(c, level, mask_of(5), side[1] + (size_t)b * ct_elems, slot(c0 + b, 5), st));
+        }
+        // second stage: C^-1 and C^+1 rotated by -W and +W (their own decompositions)
+        for (u32 sd = 0; sd < 2; sd++) {
+            const u64* base[CT_BATCH];
+            for (u32 b = 0; b < n; b++) {
+                base[b] = side[sd] + (size_t)b * ct_elems;
+                c1s[b] = base[b] + L1 * N;
+            }
+            if ((rc = run_modup(c, level, c1s, n, ws, st))) return rc;
+            for (u32 kt = 1; kt <= 7; kt += 6) {
+                const u32 t = (kt == 1 ? 0 : 6) + 2 * sd;  // corner taps 0, 2 (row -1) and 6, 8 (row +1)
+                for (u32 b = 0; b < n; b++) outs[b] = slot(c0 + b, t);
+                if (gs[kt] == 1) {
+                    for (u32 b = 0; b < n; b++) HIP_TRY(launch_mask_mul(c, level, mask_of(t), base[b], outs[b], st));
+                } else if ((rc = rotate_batch(base, n, kt, outs, mask_of(t)))) return rc;
+            }
         }
     }
     // convolution evaluation: integer-weighted sum over (input channel, tap) for every output channel

@@ -133,7 +133,7 @@ def test_ctct_mul_relin_matches_oracle(ks_setup, level):
 
 
 # ----------------------------------------------------------------------------------- convolution
-def conv_case(name, level=None, bits=50):
+def conv_case(name, level=None, bits=50, four_keys=False):
     wl = CONFIGS[name]
     p = make_params(wl.log_n, wl.num_q, wl.num_p, wl.dnum, bits=bits)
     orc, ctx = both(p)
@@ -146,9 +146,11 @@ def conv_case(name, level=None, bits=50):
     offs = conv_tap_offsets(wl.width)
     keys = {off: orc.gen_rotation_key(s, s_ntt, off, 200 + i) for i, off in enumerate(offs) if off}
     masks, w_int = orc.conv_operands(w, wl.height, wl.width, wl.batch, level, 2.0 ** 28, p.moduli[level] / 2.0 ** 28)
-    dkeys = [hx.ckks_key_load(ctx, hx.from_host(keys[off]), hx.ckks_galois_element(ctx, off)) if off else None for off in offs]
+    if four_keys:                                 # only the keys of -1, +1, -W, +W exist
+        keys = {off: k for off, k in keys.items() if off in (-1, 1, -wl.width, wl.width)}
+    dkeys = [hx.ckks_key_load(ctx, hx.from_host(keys[off]), hx.ckks_galois_element(ctx, off)) if off in keys else None for off in offs]
     outs = hx.he_conv_batched(ctx, wl.height, wl.width, wl.batch, level, [hx.from_host(c) for c in cts], dkeys,
-                              hx.from_host(masks), hx.from_host(w_residues(w_int, p.moduli, level)), wl.c_out)
+                              hx.from_host(masks), hx.from_host(w_residues(w_int, p.moduli, level)), wl.c_out, four_keys=four_keys)
     return wl, p, orc, level, s_ntt, img, w, scale, cts, keys, masks, w_int, [hx.to_host(o) for o in outs]
 
 
@@ -165,6 +167,32 @@ def test_he_conv_matches_oracle_and_float_conv(name, level, bits):
             continue    # one special prime for 2-limb digits / 36-bit primes under a 2^40 scale: limb parity only
         dec = orc.unpack_channel(orc.decrypt(outs[o], level - 1, s_ntt, scale), wl.batch, wl.height, wl.width)
         assert np.abs(dec - ref[:, o]).max() < 1e-4
+
+
+@pytest.mark.parametrize("name,level,bits", [("cfg1_single_conv", None, 50), ("small_conv", None, 50), ("small_conv", 3, 56)])
+def test_he_conv_four_key_alignment_matches_oracle(name, level, bits):
+    """The paper's two-stage input alignment with four rotation keys (Eqs. 8-10): same residues as the
+    oracle's four-key schedule, same slots as the float64 convolution."""
+    wl, p, orc, level, s_ntt, img, w, scale, cts, keys, masks, w_int, outs = conv_case(name, level, bits, four_keys=True)
+    assert len(keys) == 4
+    want = orc.he_conv(cts, level, wl.width, keys, masks, w_int, four_keys=True)
+    ref = conv2d_reference(img, w)
+    for o in range(wl.c_out):
+        assert np.array_equal(outs[o], want[o]), f"output channel {o}"
+        dec = orc.unpack_channel(orc.decrypt(outs[o], level - 1, s_ntt, scale), wl.batch, wl.height, wl.width)
+        assert np.abs(dec - ref[:, o]).max() < 1e-4
+
+
+def test_he_conv_four_keys_rejects_a_missing_key():
+    wl = CONFIGS["cfg1_single_conv"]
+    p = wl.params()
+    orc, ctx = both(p)
+    level = p.num_q - 1
+    ct = hx.from_host(rand_ct(np.random.default_rng(2), p.moduli, level, orc.N))
+    with pytest.raises(hx.CkksError) as e:
+        hx.he_conv_batched(ctx, wl.height, wl.width, wl.batch, level, [ct], [None] * 9, hx.empty(9, level + 1, orc.N),
+                           hx.empty(1, 1, 9, level + 1), 1, four_keys=True)
+    assert e.value.code == hx.binding.CKKS_ERR_NO_KEY
 
 
 def test_he_conv_equals_composition_of_exported_ops():

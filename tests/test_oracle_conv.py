@@ -143,6 +143,41 @@ def test_he_conv_unhoisted_schedule_agrees():
     assert np.array_equal(a, b)
 
 
+def test_four_key_alignment_gives_the_same_aligned_slots():
+    """The two-stage alignment with the keys {-1, +1, -W, +W} (Eqs. 8-10) and the eight direct
+    rotations decrypt to the same nine vectors: the input rolled by dy*W+dx."""
+    wl, p, o, level, s, s_ntt, img, w, scale, cts, keys = _conv_setup("small_conv", 5000)
+    W = wl.width
+    four = {off: keys[off] for off in (-1, 1, -W, W)}            # only these four keys exist
+    z = o.pack_channel(img, 0)
+    a = o.align_four_keys(cts[0], level, W, four)
+    b = o.align_direct(cts[0], level, W, keys)
+    assert len(a) == len(b) == 9
+    for t, off in enumerate(conv_tap_offsets(W)):
+        za, zb = o.decrypt(a[t], level, s_ntt, scale), o.decrypt(b[t], level, s_ntt, scale)
+        assert np.abs(za - np.roll(z, -off)).max() < 1e-5, t
+        assert np.abs(za - zb).max() < 1e-5, t
+    assert np.array_equal(a[4], b[4])                               # the centre is the input itself
+    for t in (1, 3, 5, 7):                                          # one-step taps: the very same key switch
+        assert np.array_equal(a[t], b[t]), t
+    for t in (0, 2, 6, 8):                                          # corners: two key switches, other residues
+        assert not np.array_equal(a[t], b[t]), t
+
+
+@pytest.mark.parametrize("name", ["cfg1_single_conv", "small_conv"])
+def test_he_conv_four_keys_decrypts_to_float_conv(name):
+    wl, p, o, level, s, s_ntt, img, w, scale, cts, keys = _conv_setup(name, 6000)
+    W = wl.width
+    four = {off: keys[off] for off in (-1, 1, -W, W)}
+    delta_m = 2.0 ** 28
+    M, w_int = o.conv_operands(w, wl.height, wl.width, wl.batch, level, delta_m, p.moduli[level] / delta_m)
+    outs = o.he_conv(cts, level, W, four, M, w_int, four_keys=True)
+    want = conv2d_reference(img, w)
+    for oc, ct in outs.items():
+        got = o.unpack_channel(o.decrypt(ct, level - 1, s_ntt, scale), wl.batch, wl.height, wl.width)
+        assert np.abs(got - want[:, oc]).max() < 1e-4
+
+
 def test_activation_polynomial_pins():
     assert activation_reference(np.array([0.0, 1.0, -1.0])).tolist() == [0.0, 1.0, -1.0]
     # p'(x) = 35/16 (1-x^2)^3: flat at +-1
