@@ -423,6 +423,37 @@ void orc_mul(void* h, const int* mod_idx, int n_mod, const u64* a, const u64* b,
         for (size_t x = 0; x < N; x++) out[t * N + x] = mulmod(a[t * N + x], b[t * N + x], c->mod[mod_idx[t]]);
 }
 
+// The multiply-accumulate of Eq. 11 on an explicit list of moduli (the extended basis Q_l P of a
+// convolution whose division by P comes after the sum): acc[c][t][x] (+)= sum_k pt_k[t][x] * x_k[c][t][x]
+// mod moduli[mod_idx[t]].  pts: n_terms pointers to [n_mod][N]; xs: n_terms pointers to [2][n_mod][N].
+void orc_mac_on_moduli(void* h, const int* mod_idx, int n_mod, int n_terms, const u64* const* pts, const u64* const* xs, u64* acc,
+                       int accumulate) {
+    Ctx* c = (Ctx*)h;
+    size_t N = c->N;
+#pragma omp parallel for collapse(2)
+    for (int comp = 0; comp < 2; comp++)
+        for (int t = 0; t < n_mod; t++) {
+            u64 q = c->mod[mod_idx[t]];
+            u64* a = acc + ((size_t)comp * n_mod + t) * N;
+            if (!accumulate) for (size_t x = 0; x < N; x++) a[x] = 0;
+            for (int k = 0; k < n_terms; k++) {
+                const u64* p = pts[k] + (size_t)t * N;
+                const u64* v = xs[k] + ((size_t)comp * n_mod + t) * N;
+                for (size_t x = 0; x < N; x++) a[x] = addmod(a[x], mulmod(p[x], v[x], q), q);
+            }
+        }
+}
+
+// poly[t][x] * scalar[t] mod moduli[mod_idx[t]] (an integer scalar given by its residues).
+void orc_scalar_mul_on_moduli(void* h, const int* mod_idx, int n_mod, int n_comp, const u64* poly, const u64* scalar, u64* out) {
+    Ctx* c = (Ctx*)h;
+    size_t N = c->N;
+    for (int comp = 0; comp < n_comp; comp++)
+        for (int t = 0; t < n_mod; t++)
+            for (size_t x = 0; x < N; x++)
+                out[((size_t)comp * n_mod + t) * N + x] = mulmod(poly[((size_t)comp * n_mod + t) * N + x], scalar[t], c->mod[mod_idx[t]]);
+}
+
 void orc_add(void* h, int level, int n_comp, const u64* a, const u64* b, u64* out) {
     Ctx* c = (Ctx*)h;
     size_t N = c->N, L1 = level + 1;

@@ -439,6 +439,98 @@ class Oracle:
         down = [self.rotate(b, level, +W, rot_keys[+W], True, d) for b, d in ((cm, dm), (ct, d0), (cp, dp))]
         return up + [cm, ct, cp] + down
 
+    # ---- the same layer with the division by P taken once, after the sum (deferred ModDown) ----------
+    def special_product_residues(self, level: int) -> np.ndarray:
+        """[P]_{q_i} for i <= level and 0 for the special primes: P = p_0 ... p_{k-1} on the extended basis."""
+        P = 1
+        for t in range(self.num_q, self.M):
+            P *= self.moduli[t]
+        return np.array([P % self.moduli[t] for t in self.ext_moduli_idx(level)], dtype=np.uint64)
+
+    def scalar_residues_ext(self, value: int, level: int) -> np.ndarray:
+        return np.array([int(value) % self.moduli[t] for t in self.ext_moduli_idx(level)], dtype=np.uint64)
+
+    def scalar_mul_ext(self, poly, scalar_res, level: int) -> np.ndarray:
+        """poly [n_comp, E, N] (or [E, N]) on the extended basis times an integer scalar given by residues."""
+        poly = _u64(poly)
+        idx = np.array(self.ext_moduli_idx(level), dtype=np.int32)
+        n_comp = poly.size // (len(idx) * self.N)
+        out = np.empty_like(poly)
+        self.lib.orc_scalar_mul_on_moduli(self.h, _p(idx), len(idx), n_comp, _p(poly), _p(_u64(scalar_res)), _p(out))
+        return out
+
+    def mac_ext(self, pts: Sequence[np.ndarray], xs: Sequence[np.ndarray], level: int) -> np.ndarray:
+        """sum_k pt_k (.) x_k on the extended basis Q_level P: pts [E][N], xs [2][E][N]."""
+        idx = np.array(self.ext_moduli_idx(level), dtype=np.int32)
+        E = len(idx)
+        pts = [_u64(p_) for p_ in pts]
+        xs = [_u64(x_) for x_ in xs]
+        for p_, x_ in zip(pts, xs):
+            assert p_.shape == (E, self.N) and x_.shape == (2, E, self.N)
+        n = len(pts)
+        out = np.empty((2, E, self.N), dtype=np.uint64)
+        pa = (C.c_void_p * n)(*[p_.ctypes.data for p_ in pts])
+        xa = (C.c_void_p * n)(*[x_.ctypes.data for x_ in xs])
+        self.lib.orc_mac_on_moduli(self.h, _p(idx), E, n, pa, xa, _p(out), 0)
+        return out
+
+    def conv_operands_ext(self, weights: np.ndarray, height: int, width: int, batch: int, level: int,
+                          delta_m: float, delta_w: float) -> Tuple[np.ndarray, np.ndarray]:
+        """As conv_operands, with the mask plaintexts on the extended basis: M [9][level+1+k][N]."""
+        masks = self.tap_masks(height, width, batch)
+        ext = self.ext_moduli_idx(level)
+        M = np.stack([self.lift_ntt(self.encode(masks[t], delta_m), ext) for t in range(9)])
+        w_int = round_half_away(np.asarray(weights, dtype=np.float64).reshape(weights.shape[0], weights.shape[1], 9) * delta_w).astype(np.int64)
+        return M, w_int
+
+    def align_deferred(self, ct, level: int, width: int, rot_keys: Dict[int, np.ndarray]) -> List[np.ndarray]:
+        """The nine aligned copies of one channel ciphertext BEFORE their division by P, on the
+        extended basis Q_level P ([2][level+1+k][N] each): for tap offset r != 0 with g = 5^r
+            X_r = (P * sigma_g(c0) + v_0,  v_1),   v = < sigma_g(ModUp(c1)), key_g >,
+        so that ModDown(X_r) = Rot(ct, r); the centre tap is P * ct (zero on the special primes)."""
+        ct = _u64(ct)
+        L1, E = level + 1, level + 1 + self.num_p
+        digits = self.modup(ct[1], level)
+        Pres = self.special_product_residues(level)
+        row = []
+        for dy in (-1, 0, 1):
+            for dx in (-1, 0, 1):
+                off = dy * width + dx
+                x = np.zeros((2, E, self.N), dtype=np.uint64)
+                if off % self.n == 0:
+                    x[:, :L1] = self.scalar_mul(ct, Pres[:L1], level)
+                else:
+                    g = self.galois(off)
+                    v = self.key_inner(self.automorph_ntt(digits, g), rot_keys[off], level)
+                    pc0 = self.scalar_mul(self.automorph_ntt(ct[0], g), Pres[:L1], level)
+                    x[:] = v
+                    x[0, :L1] = self.add(v[0, :L1], pc0, level)
+                row.append(x)
+        return row
+
+    def he_conv_deferred(self, cts: Sequence[np.ndarray], level: int, width: int, rot_keys: Dict[int, np.ndarray],
+                         M_ext: np.ndarray, w_int: np.ndarray, out_channels: Optional[Iterable[int]] = None) -> Dict[int, np.ndarray]:
+        """The batched convolution layer (Eqs. 10-11) with one division by P per OUTPUT channel
+        instead of one per rotation:
+            out_o = Rescale( ModDown( sum_c sum_tap pt[o,c,tap] (.) X_tap(ct_c) ) ),
+        the sum taken on the extended basis Q_level P, X_tap as in align_deferred, the plaintexts
+        pt = w_int * M_tap on that basis too.  Same slots as he_conv up to rounding noise (a little
+        less of it: one rounding after the sum instead of one per term), different residues."""
+        C_in = len(cts)
+        aligned = [self.align_deferred(cts[c], level, width, rot_keys) for c in range(C_in)]
+        outs = {}
+        chans = range(w_int.shape[0]) if out_channels is None else out_channels
+        for o in chans:
+            pts, terms = [], []
+            for c in range(C_in):
+                for t in range(9):
+                    pts.append(self.scalar_mul_ext(M_ext[t], self.scalar_residues_ext(int(w_int[o, c, t]), level), level))
+                    terms.append(aligned[c][t])
+            acc = self.mac_ext(pts, terms, level)
+            u = np.stack([self.moddown(acc[0], level), self.moddown(acc[1], level)])
+            outs[o] = self.rescale(u, level)
+        return outs
+
     def he_conv(self, cts: Sequence[np.ndarray], level: int, width: int, rot_keys: Dict[int, np.ndarray],
                 M: np.ndarray, w_int: np.ndarray, out_channels: Optional[Iterable[int]] = None,
                 hoisted: bool = True, four_keys: bool = False) -> Dict[int, np.ndarray]:

@@ -178,6 +178,72 @@ def test_he_conv_four_keys_decrypts_to_float_conv(name):
         assert np.abs(got - want[:, oc]).max() < 1e-4
 
 
+def test_mac_on_extended_basis_matches_python_integers(tiny_params):
+    o = Oracle(tiny_params)
+    level = 1                                                    # extended basis: q_0, q_1, p_0, p_1
+    ext = o.ext_moduli_idx(level)
+    assert ext == [0, 1, 3, 4]
+    rng = np.random.default_rng(6)
+    pts = [np.stack([rng.integers(0, o.moduli[t], o.N, dtype=np.uint64) for t in ext]) for _ in range(5)]
+    xs = [np.stack([np.stack([rng.integers(0, o.moduli[t], o.N, dtype=np.uint64) for t in ext]) for _ in range(2)]) for _ in range(5)]
+    got = o.mac_ext(pts, xs, level)
+    for comp in range(2):
+        for e, t in enumerate(ext):
+            q = o.moduli[t]
+            want = [sum(int(pts[k][e][x]) * int(xs[k][comp][e][x]) for k in range(5)) % q for x in range(o.N)]
+            assert got[comp, e].tolist() == want
+    P = o.moduli[3] * o.moduli[4]
+    assert o.special_product_residues(level).tolist() == [P % o.moduli[0], P % o.moduli[1], 0, 0]
+    assert o.scalar_residues_ext(-3, level).tolist() == [o.moduli[t] - 3 for t in ext]
+    sm = o.scalar_mul_ext(xs[0], o.scalar_residues_ext(-3, level), level)
+    assert sm[1, 2].tolist() == [(-3 * int(v)) % o.moduli[3] for v in xs[0][1][2]]
+
+
+def test_deferred_moddown_alignment_is_the_rotation_times_P():
+    """ModDown of each pre-division aligned copy is the hoisted rotation itself (same residues), and
+    on tiny parameters the copy is congruent to P * Rot modulo every q_i up to the rounding part."""
+    wl, p, o, level, s, s_ntt, img, w, scale, cts, keys = _conv_setup("small_conv", 7000)
+    a = o.align_deferred(cts[0], level, wl.width, keys)
+    b = o.align_direct(cts[0], level, wl.width, keys)
+    E = level + 1 + o.num_p
+    for t in range(9):
+        assert a[t].shape == (2, E, o.N)
+        got = np.stack([o.moddown(a[t][0], level), o.moddown(a[t][1], level)])
+        assert np.array_equal(got, b[t]), t
+    assert not a[4][:, level + 1:].any()                        # centre: P * ct vanishes on the special primes
+
+
+@pytest.mark.parametrize("name", ["cfg1_single_conv", "small_conv"])
+def test_he_conv_deferred_moddown_decrypts_to_float_conv(name):
+    wl, p, o, level, s, s_ntt, img, w, scale, cts, keys = _conv_setup(name, 8000)
+    delta_m = 2.0 ** 28
+    delta_w = p.moduli[level] / delta_m
+    M_ext, w_int = o.conv_operands_ext(w, wl.height, wl.width, wl.batch, level, delta_m, delta_w)
+    M, w_int2 = o.conv_operands(w, wl.height, wl.width, wl.batch, level, delta_m, delta_w)
+    assert np.array_equal(M_ext[:, :level + 1], M) and np.array_equal(w_int, w_int2)
+    outs = o.he_conv_deferred(cts, level, wl.width, keys, M_ext, w_int)
+    direct = o.he_conv(cts, level, wl.width, keys, M, w_int)
+    want = conv2d_reference(img, w)
+    for oc, ct in outs.items():
+        z = o.decrypt(ct, level - 1, s_ntt, scale)
+        assert np.abs(o.unpack_channel(z, wl.batch, wl.height, wl.width) - want[:, oc]).max() < 1e-4
+        assert np.abs(z - o.decrypt(direct[oc], level - 1, s_ntt, scale)).max() < 1e-5
+        assert not np.array_equal(ct, direct[oc])                # one rounding instead of many: other residues
+
+
+def test_he_conv_deferred_centre_only_kernel_equals_direct():
+    """With only the centre weight nothing is rotated: ModDown(P * y) = y exactly, so both schedules
+    must give the very same residues."""
+    wl, p, o, level, s, s_ntt, img, w, scale, cts, keys = _conv_setup("cfg1_single_conv", 9000)
+    w = np.zeros_like(w)
+    w[0, 0, 1, 1] = -0.4375
+    delta_m = 2.0 ** 28
+    M_ext, w_int = o.conv_operands_ext(w, wl.height, wl.width, wl.batch, level, delta_m, p.moduli[level] / delta_m)
+    a = o.he_conv_deferred(cts, level, wl.width, keys, M_ext, w_int)[0]
+    b = o.he_conv(cts, level, wl.width, keys, M_ext[:, :level + 1], w_int)[0]
+    assert np.array_equal(a, b)
+
+
 def test_activation_polynomial_pins():
     assert activation_reference(np.array([0.0, 1.0, -1.0])).tolist() == [0.0, 1.0, -1.0]
     # p'(x) = 35/16 (1-x^2)^3: flat at +-1
