@@ -152,15 +152,23 @@ int ckks_ctct_mul_relin(const ckks_ctx* ctx, const uint64_t* d_a, const uint64_t
  * uint64[2][level][N].  Fails with CKKS_ERR_INVALID_ARG if H*W*batch > N/2 (Eq. 4). */
 typedef enum he_conv_alignment {
     HE_CONV_ALIGN_DIRECT = 0,   /* eight rotations of the input by dy*W+dx, eight keys, one decomposition */
-    HE_CONV_ALIGN_FOUR_KEYS = 1 /* the paper's input alignment (Eqs. 8-10): C^-1 = Rot(in,-1), C^+1 =
+    HE_CONV_ALIGN_FOUR_KEYS = 1,/* the paper's input alignment (Eqs. 8-10): C^-1 = Rot(in,-1), C^+1 =
                                    Rot(in,+1), then Rot(.,-W) and Rot(.,+W) of C^-1, in, C^+1; only the keys
                                    of -1, +1, -W, +W (rot_keys entries 3, 5, 1, 7) are read; three
                                    decompositions per input; half the resident key bytes */
+    HE_CONV_DEFERRED_MODDOWN = 2/* eight direct rotations as in DIRECT, but the division by P that ends each
+                                   key switch is taken once per OUTPUT channel, after the sum of Eq. 11:
+                                     X_tap(in) = (P * sigma_g(c0) + v_0, v_1),  v = <sigma_g(ModUp(c1)), key_g>
+                                     out_o = Rescale( ModDown( sum_c sum_tap pt[o,c,tap] (.) X_tap(in_c) ) )
+                                   on the extended basis q_0..q_level, p_0..p_{k-1}.  In this mode
+                                   d_tap_masks is uint64[9][level+1+num_p][N] and d_w_res is
+                                   uint64[C_out][C_in][9][level+1+num_p] (residues modulo the special primes
+                                   appended); C_out ModDowns instead of 8*C_in, one rounding per output */
 } he_conv_alignment;
 
 typedef struct he_conv_desc {
     uint32_t c_in, c_out, height, width, batch, level;
-    uint32_t alignment; /* he_conv_alignment; both give the same slots up to noise, different residues */
+    uint32_t alignment; /* he_conv_alignment; all give the same slots up to noise, different residues */
 } he_conv_desc;
 
 /* Workspace bytes he_conv_batched needs for this shape (0 on invalid arguments): the shared

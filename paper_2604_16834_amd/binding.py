@@ -32,6 +32,10 @@ CKKS_OP_RESCALE = 2
 CKKS_OP_CTCT_MUL_RELIN = 3
 CKKS_OP_POLY_ACT = 5
 
+HE_CONV_ALIGN_DIRECT = 0
+HE_CONV_ALIGN_FOUR_KEYS = 1
+HE_CONV_DEFERRED_MODDOWN = 2
+
 EXPORTS = (
     "ckks_ctx_create", "ckks_ctx_destroy", "ckks_last_error_string", "ckks_workspace_bytes",
     "ckks_ntt_fwd", "ckks_ntt_inv", "ckks_key_load", "ckks_key_free", "ckks_galois_element",
@@ -295,24 +299,27 @@ def ckks_ctct_mul_relin(ctx: Context, a: torch.Tensor, b: torch.Tensor, level: i
 
 
 def he_conv_workspace_bytes(ctx: Context, c_in: int, c_out: int, height: int, width: int, batch: int, level: int,
-                            four_keys: bool = False) -> int:
-    d = _ConvDesc(c_in, c_out, height, width, batch, level, int(bool(four_keys)))
+                            alignment: int = HE_CONV_ALIGN_DIRECT) -> int:
+    d = _ConvDesc(c_in, c_out, height, width, batch, level, int(alignment))
     return int(_lib.he_conv_workspace_bytes(ctx.handle, C.byref(d)))
 
 
 def he_conv_batched(ctx: Context, height: int, width: int, batch: int, level: int, ins: Sequence[torch.Tensor],
                     rot_keys: Sequence[Optional[Key]], tap_masks: torch.Tensor, w_res: torch.Tensor, c_out: int,
                     outs: Optional[List[torch.Tensor]] = None, ws: Optional[torch.Tensor] = None, stream=None,
-                    four_keys: bool = False) -> List[torch.Tensor]:
-    """four_keys: the paper's four-key two-stage input alignment instead of eight direct rotations.
+                    alignment: int = HE_CONV_ALIGN_DIRECT) -> List[torch.Tensor]:
+    """alignment: HE_CONV_ALIGN_DIRECT (eight hoisted rotations), HE_CONV_ALIGN_FOUR_KEYS (the paper's two-stage
+    alignment with four keys) or HE_CONV_DEFERRED_MODDOWN (one division by P per output channel).
     ins: C_in tensors [2][level+1][N]; rot_keys: nine entries in tap order (centre ignored);
-    tap_masks [9][level+1][N]; w_res [C_out][C_in][9][level+1] residues of the integer weights."""
+    tap_masks [9][L][N]; w_res [C_out][C_in][9][L] residues of the integer weights, L = level+1 limbs
+    (level+1+num_p, the extended basis, for HE_CONV_DEFERRED_MODDOWN)."""
     c_in = len(ins)
     L1 = level + 1
     if len(rot_keys) != 9:
         raise ValueError("nine rotation-key entries expected (row-major taps, centre may be None)")
-    if tap_masks.numel() != 9 * L1 * ctx.N or w_res.numel() != c_out * c_in * 9 * L1:
-        raise ValueError("tap_masks must be [9][level+1][N] and w_res [C_out][C_in][9][level+1]")
+    LM = L1 + ctx.num_p if alignment == HE_CONV_DEFERRED_MODDOWN else L1
+    if tap_masks.numel() != 9 * LM * ctx.N or w_res.numel() != c_out * c_in * 9 * LM:
+        raise ValueError("tap_masks must be [9][L][N] and w_res [C_out][C_in][9][L], L = %d limbs" % LM)
     for t in ins:
         if t.numel() != 2 * L1 * ctx.N:
             raise ValueError("each input must be [2][level+1][N]")
@@ -321,8 +328,8 @@ def he_conv_batched(ctx: Context, height: int, width: int, batch: int, level: in
     for o in outs:
         if o.numel() != 2 * level * ctx.N:
             raise ValueError("each output must be [2][level][N]")
-    d = _ConvDesc(c_in, c_out, height, width, batch, level, int(bool(four_keys)))
-    ws = _ws(ctx, ws, he_conv_workspace_bytes(ctx, c_in, c_out, height, width, batch, level, four_keys))
+    d = _ConvDesc(c_in, c_out, height, width, batch, level, int(alignment))
+    ws = _ws(ctx, ws, he_conv_workspace_bytes(ctx, c_in, c_out, height, width, batch, level, alignment))
     ia = _ptr_array([_ptr(t) for t in ins])
     ka = _ptr_array([k.handle.value if k is not None else None for k in rot_keys])
     oa = _ptr_array([_ptr(o) for o in outs])

@@ -175,6 +175,65 @@ size_t ws_poly_act(const ckks_ctx* c, u32 level, u32 n) {
            blk(2 * (size_t)n * (level + 1) * N) + ws_ctct(c, level, n) + ws_rescale(c, level, n);
 }
 
+// The convolution with one division by P per output channel: every aligned copy stays on the extended
+// basis Q_level P (inner product + P * sigma_g(c0), times the tap's mask), the sum over (input channel,
+// tap) is taken there, and only the C_out sums go through ModDown and the rescale.  gs: Galois
+// elements of the nine taps (1 = no rotation); masks [9][E][N], w_res [C_out][C_in][9][E].
+int conv_deferred(const ckks_ctx* c, const he_conv_desc* d, const u32* gs, const uint64_t* const* h_d_in,
+                  const ckks_key* const* rot_keys, const u64* masks, const u64* w_res, uint64_t* const* h_d_out, void* d_ws,
+                  size_t ws_bytes, hipStream_t st) {
+    const u32 level = d->level, E = c->ext_limbs(level);
+    const size_t N = c->N, L1 = level + 1, ct_elems = 2 * L1 * N, x_elems = 2 * (size_t)E * N;
+    Arena ar(d_ws, ws_bytes);
+    KsWs ws;
+    bool ok = carve_ks(c, level, CT_BATCH, CT_BATCH, ar, ws);
+    u64* xs = ar.take((size_t)d->c_in * 9 * x_elems);
+    u64* acc = ar.take((size_t)d->c_out * x_elems);
+    u64* wscratch = ar.take(weighted_sum_scratch_elems(c, E, d->c_in * 9, d->c_out));
+    u64* tmp = ar.take((size_t)CT_BATCH * ct_elems);
+    if (!ok || !ar.ok() || ar.used + ws_rescale(c, level, CT_BATCH) > ar.cap)
+        return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for the convolution");
+    for (u32 c0 = 0; c0 < d->c_in; c0 += CT_BATCH) {
+        const u32 n = d->c_in - c0 < CT_BATCH ? d->c_in - c0 : CT_BATCH;
+        const u64 *in[CT_BATCH], *c1s[CT_BATCH];
+        u64* outs[CT_BATCH];
+        for (u32 b = 0; b < n; b++) {
+            in[b] = (const u64*)h_d_in[c0 + b];
+            c1s[b] = in[b] + L1 * N;
+        }
+        int rc = run_modup(c, level, c1s, n, ws, st);
+        if (rc) return rc;
+        for (u32 t = 0; t < 9; t++) {
+            const u64* mask = masks + (size_t)t * E * N;
+            for (u32 b = 0; b < n; b++) outs[b] = xs + ((size_t)(c0 + b) * 9 + t) * x_elems;
+            if (gs[t] == 1) {
+                for (u32 b = 0; b < n; b++) HIP_TRY(launch_centre_ext(c, level, mask, in[b], outs[b], st));
+                continue;
+            }
+            HIP_TRY(launch_key_inner_ext(c, level, ws.digits, ws.dig_b, rot_keys[t]->d_key, gs[t], in, mask, outs, n, st));
+        }
+    }
+    HIP_TRY(launch_weighted_sum(c, level, true, xs, d->c_in * 9, w_res, d->c_out, acc, wscratch, st));
+    for (u32 o0 = 0; o0 < d->c_out; o0 += CT_BATCH) {
+        const u32 n = d->c_out - o0 < CT_BATCH ? d->c_out - o0 : CT_BATCH;
+        KsWs wd = ws;
+        wd.v = acc + (size_t)o0 * x_elems;  // the sums take the place of a batch of inner products
+        wd.v_b = x_elems;
+        FinalItem items[CT_BATCH];
+        const u64* ins[CT_BATCH];
+        u64* outs[CT_BATCH];
+        for (u32 b = 0; b < n; b++) {
+            items[b] = FinalItem{nullptr, nullptr, nullptr, tmp + (size_t)b * ct_elems, 1, 0};
+            ins[b] = tmp + (size_t)b * ct_elems;
+            outs[b] = (u64*)h_d_out[o0 + b];
+        }
+        int rc = run_moddown(c, level, wd, n, items, st);
+        if (rc) return rc;
+        if ((rc = run_rescale(c, level, ins, L1 * N, outs, n, ar.rest(), st))) return rc;
+    }
+    return CKKS_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -196,8 +255,14 @@ size_t ckks_workspace_bytes(const ckks_ctx* c, int op, uint32_t level, uint32_t 
 size_t he_conv_workspace_bytes(const ckks_ctx* c, const he_conv_desc* d) {
     if (!c || !d || !c->dnum || !level_ok(c, d->level) || d->level < 1) return 0;
     const size_t N = c->N, L1 = d->level + 1;
+    if (d->alignment == HE_CONV_DEFERRED_MODDOWN) {
+        const size_t E = c->ext_limbs(d->level);
+        return ws_ks(c, d->level, CT_BATCH, CT_BATCH) + blk((size_t)d->c_in * 9 * 2 * E * N) + blk((size_t)d->c_out * 2 * E * N) +
+               blk(weighted_sum_scratch_elems(c, (u32)E, d->c_in * 9, d->c_out)) + blk((size_t)CT_BATCH * 2 * L1 * N) +
+               ws_rescale(c, d->level, CT_BATCH);
+    }
     return ws_ks(c, d->level, CT_BATCH, CT_BATCH) + blk((size_t)d->c_in * 9 * 2 * L1 * N) + blk((size_t)d->c_out * 2 * L1 * N) +
-           blk(weighted_sum_scratch_elems(c, d->level, d->c_in * 9, d->c_out)) + ws_rescale(c, d->level, CT_BATCH) +
+           blk(weighted_sum_scratch_elems(c, (u32)L1, d->c_in * 9, d->c_out)) + ws_rescale(c, d->level, CT_BATCH) +
            (d->alignment == HE_CONV_ALIGN_FOUR_KEYS ? 2 * blk((size_t)CT_BATCH * 2 * L1 * N) : 0);
 }
 
@@ -397,7 +462,7 @@ int he_conv_batched(const ckks_ctx* c, const he_conv_desc* d, const uint64_t* co
         return set_err(c, CKKS_ERR_INVALID_ARG, "empty convolution shape");
     if (!level_ok(c, d->level) || d->level < 1) return set_err(c, CKKS_ERR_LEVEL_MISMATCH, "convolution needs 1 <= level < num_q");
     if ((u64)d->height * d->width * d->batch > c->N / 2) return set_err(c, CKKS_ERR_INVALID_ARG, "H*W*batch exceeds the N/2 slots");
-    if (d->alignment != HE_CONV_ALIGN_DIRECT && d->alignment != HE_CONV_ALIGN_FOUR_KEYS)
+    if (d->alignment != HE_CONV_ALIGN_DIRECT && d->alignment != HE_CONV_ALIGN_FOUR_KEYS && d->alignment != HE_CONV_DEFERRED_MODDOWN)
         return set_err(c, CKKS_ERR_INVALID_ARG, "unknown alignment");
     const bool four = d->alignment == HE_CONV_ALIGN_FOUR_KEYS;
     const u32 level = d->level;
@@ -417,12 +482,15 @@ int he_conv_batched(const ckks_ctx* c, const he_conv_desc* d, const uint64_t* co
     for (u32 i = 0; i < d->c_in; i++) if (!h_d_in[i]) return set_err(c, CKKS_ERR_INVALID_ARG, "null input ciphertext");
     for (u32 o = 0; o < d->c_out; o++) if (!h_d_out[o]) return set_err(c, CKKS_ERR_INVALID_ARG, "null output ciphertext");
 
+    if (d->alignment == HE_CONV_DEFERRED_MODDOWN)
+        return conv_deferred(c, d, gs, h_d_in, rot_keys, (const u64*)d_tap_masks, (const u64*)d_w_res, h_d_out, d_ws, ws_bytes,
+                             (hipStream_t)stream);
     Arena ar(d_ws, ws_bytes);
     KsWs ws;
     bool ok = carve_ks(c, level, CT_BATCH, CT_BATCH, ar, ws);
     u64* xs = ar.take((size_t)d->c_in * 9 * ct_elems);
     u64* acc = ar.take((size_t)d->c_out * ct_elems);
-    u64* wscratch = ar.take(weighted_sum_scratch_elems(c, level, d->c_in * 9, d->c_out));
+    u64* wscratch = ar.take(weighted_sum_scratch_elems(c, (u32)L1, d->c_in * 9, d->c_out));
     u64* side[2] = {nullptr, nullptr};  // C^-1 and C^+1 of the current batch (four-key alignment)
     if (four) {
         side[0] = ar.take((size_t)CT_BATCH * ct_elems);
@@ -503,7 +571,7 @@ int he_conv_batched(const ckks_ctx* c, const he_conv_desc* d, const uint64_t* co
         }
     }
     // convolution evaluation: integer-weighted sum over (input channel, tap) for every output channel
-    HIP_TRY(launch_weighted_sum(c, level, xs, d->c_in * 9, (const u64*)d_w_res, d->c_out, acc, wscratch, st));
+    HIP_TRY(launch_weighted_sum(c, level, false, xs, d->c_in * 9, (const u64*)d_w_res, d->c_out, acc, wscratch, st));
     for (u32 o0 = 0; o0 < d->c_out; o0 += CT_BATCH) {
         const u32 n = d->c_out - o0 < CT_BATCH ? d->c_out - o0 : CT_BATCH;
         const u64* ins[CT_BATCH];

@@ -136,6 +136,8 @@ hipError_t launch_modup_conv(const ckks_ctx* c, u32 level, u32 j, const u64* y, 
 hipError_t launch_key_inner(const ckks_ctx* c, u32 level, const u64* digits, const u64* key, u32 g, u64* v, hipStream_t st);
 hipError_t launch_key_inner_multi(const ckks_ctx* c, u32 level, const u64* digits, size_t digits_bstride, const u64* key, u32 g,
                                   u64* v, size_t v_bstride, u32 n, hipStream_t st);
+hipError_t launch_key_inner_ext(const ckks_ctx* c, u32 level, const u64* digits, size_t digits_bstride, const u64* key, u32 g,
+                                const u64* const* c0s, const u64* mask, u64* const* outs, u32 n, hipStream_t st);
 hipError_t launch_moddown_conv(const ckks_ctx* c, u32 level, const u64* v, u64* w, u32 batch, hipStream_t st);
 hipError_t launch_moddown_final(const ckks_ctx* c, u32 level, const u64* v, const u64* w, const FinalItem* items, u32 n, hipStream_t st);
 // pointwise.hip
@@ -149,9 +151,10 @@ hipError_t launch_rescale_final(const ckks_ctx* c, u32 level, const PtrList8& ct
 hipError_t launch_tensor(const ckks_ctx* c, u32 level, const PtrList8& a, size_t a_cstride, const PtrList8& b, size_t b_cstride,
                          u64* d0, u64* d1, u64* d2, u32 n, hipStream_t st);
 hipError_t launch_mask_mul(const ckks_ctx* c, u32 level, const u64* mask, const u64* ct, u64* out, hipStream_t st);
-size_t weighted_sum_scratch_elems(const ckks_ctx* c, u32 level, u32 n_terms, u32 c_out);
-hipError_t launch_weighted_sum(const ckks_ctx* c, u32 level, const u64* xs, u32 n_terms, const u64* w_res, u32 c_out, u64* acc,
-                               u64* scratch, hipStream_t st);
+hipError_t launch_centre_ext(const ckks_ctx* c, u32 level, const u64* mask, const u64* ct, u64* out, hipStream_t st);
+size_t weighted_sum_scratch_elems(const ckks_ctx* c, u32 n_limbs, u32 n_terms, u32 c_out);
+hipError_t launch_weighted_sum(const ckks_ctx* c, u32 level, bool extended, const u64* xs, u32 n_terms, const u64* w_res, u32 c_out,
+                               u64* acc, u64* scratch, hipStream_t st);
 hipError_t launch_lincomb2(const ckks_ctx* c, u32 level, const PtrList8& a, size_t a_cstride, const u64* ka, const PtrList8& b,
                            size_t b_cstride, const u64* kb, const u64* add, size_t add_bstride, u64* out, size_t out_bstride, u32 n,
                            hipStream_t st);

@@ -231,6 +231,90 @@ hipError_t launch_key_inner_multi(const ckks_ctx* c, u32 level, const u64* digit
     return hipGetLastError();
 }
 
+// The inner product of a batch, finished for a convolution that divides by P once, after its sum
+// over (input channel, tap): the aligned copy of ciphertext b before its ModDown, times the tap's mask,
+//   out_b[comp][e][x] = mask[e][x] * ( v_b[comp][e][x] + (comp == 0 && e <= level ? [P]_{q_e} * c0_b[e][sigma_g x] : 0) )
+// on all E limbs of the extended basis (mask [E][N] on that basis too); P * sigma_g(c0) vanishes on the
+// special primes.  P * c0 joins the unreduced 128-bit sum as one more term.
+struct ExtItems {
+    const u64* c0[KS_MAX_BATCH];
+    u64* out[KS_MAX_BATCH];
+};
+
+__global__ __launch_bounds__(KS_THREADS) void key_inner_ext_kernel(const u64* __restrict__ digits, size_t digits_bstride,
+                                                                   const u64* __restrict__ key, ExtItems items,
+                                                                   const u64* __restrict__ mask, const u64* __restrict__ negp,
+                                                                   const ModConst* __restrict__ mc, u32 log_n, u32 level, u32 num_q,
+                                                                   u32 M, u32 E, u32 beta, u32 g, u32 n) {
+    const u32 N = 1u << log_n;
+    const u32 x = blockIdx.x * KS_THREADS + threadIdx.x;
+    if (x >= N) return;
+    const u32 e = blockIdx.y;
+    const u32 t = e <= level ? e : num_q + (e - level - 1);
+    const u32 xs = g == 1 ? x : galois_gather_index(x, g, log_n);
+    const ModConst m = mc[t];
+    const u64 mk = mask[(size_t)e * N + x];
+    const bool has_c0 = e <= level;
+    const u64 pres = has_c0 ? m.q - negp[e] : 0;  // P mod q_e
+    if (beta <= 4) {
+        u64 k0[4], k1[4];
+#pragma unroll
+        for (u32 j = 0; j < 4; j++) {
+            k0[j] = j < beta ? key[(((size_t)j * 2 + 0) * M + t) * N + x] : 0;
+            k1[j] = j < beta ? key[(((size_t)j * 2 + 1) * M + t) * N + x] : 0;
+        }
+        for (u32 b = 0; b < n; b++) {
+            const u64* d = digits + b * digits_bstride;
+            U128 acc0 = {0, 0}, acc1 = {0, 0};
+#pragma unroll
+            for (u32 j = 0; j < 4; j++) {
+                const u64 dv = j < beta ? d[((size_t)j * E + e) * N + xs] : 0;
+                acc_wide(acc0, dv, k0[j]);
+                acc_wide(acc1, dv, k1[j]);
+            }
+            if (has_c0) acc_wide(acc0, items.c0[b][(size_t)e * N + xs], pres);
+            u64* ob = items.out[b];
+            ob[((size_t)0 * E + e) * N + x] = mulmod_barrett(barrett_reduce(acc0, m), mk, m);
+            ob[((size_t)1 * E + e) * N + x] = mulmod_barrett(barrett_reduce(acc1, m), mk, m);
+        }
+        return;
+    }
+    for (u32 b = 0; b < n; b++) {
+        const u64* d = digits + b * digits_bstride;
+        U128 acc0 = {0, 0}, acc1 = {0, 0};
+        for (u32 j = 0; j < beta; j++) {
+            const u64 dv = d[((size_t)j * E + e) * N + xs];
+            acc_wide(acc0, dv, key[(((size_t)j * 2 + 0) * M + t) * N + x]);
+            acc_wide(acc1, dv, key[(((size_t)j * 2 + 1) * M + t) * N + x]);
+            if ((j & 15) == 15) {
+                acc0.lo = barrett_reduce(acc0, m); acc0.hi = 0;
+                acc1.lo = barrett_reduce(acc1, m); acc1.hi = 0;
+            }
+        }
+        if (has_c0) acc_wide(acc0, items.c0[b][(size_t)e * N + xs], pres);
+        u64* ob = items.out[b];
+        ob[((size_t)0 * E + e) * N + x] = mulmod_barrett(barrett_reduce(acc0, m), mk, m);
+        ob[((size_t)1 * E + e) * N + x] = mulmod_barrett(barrett_reduce(acc1, m), mk, m);
+    }
+}
+
+// c0s / outs: host arrays of n <= KS_MAX_BATCH device pointers ([level+1][N] and [2][E][N])
+hipError_t launch_key_inner_ext(const ckks_ctx* c, u32 level, const u64* digits, size_t digits_bstride, const u64* key, u32 g,
+                                const u64* const* c0s, const u64* mask, u64* const* outs, u32 n, hipStream_t st) {
+    const u32 E = c->ext_limbs(level), beta = c->live_digits(level);
+    ExtItems items;
+    for (u32 b = 0; b < KS_MAX_BATCH; b++) {
+        items.c0[b] = b < n ? c0s[b] : nullptr;
+        items.out[b] = b < n ? outs[b] : nullptr;
+    }
+    const u64* negp = c->d_moddown + 2 * c->k_pad + (size_t)c->k_pad * c->num_q + 2 * c->num_q;
+    dim3 grid((c->N + KS_THREADS - 1) / KS_THREADS, E);
+    ProfScope ps__(c, K_KEY_INNER, st, 8.0 * c->N * (E * (2.0 * beta + 1.0 + n * (beta + 2.0)) + n * (level + 1.0)), 2.0 * n * c->N * E * (beta + 1.0));
+    hipLaunchKernelGGL(key_inner_ext_kernel, grid, dim3(KS_THREADS), 0, st, digits, digits_bstride, key, items, mask, negp, c->d_mc,
+                       c->log_n, level, c->num_q, c->M, E, beta, g, n);
+    return hipGetLastError();
+}
+
 // ---- ModDown, conversion of the P-part ----------------------------------------------------------
 // v [2][E][N]: limbs level+1.. hold the P-part in coefficient form.  w [2][level+1][N] (coefficients)
 #define MODDOWN_LIMBS_PER_BLOCK 12

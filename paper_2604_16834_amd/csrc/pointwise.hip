@@ -170,19 +170,44 @@ hipError_t launch_mask_mul(const ckks_ctx* c, u32 level, const u64* mask, const 
     return hipGetLastError();
 }
 
+// The centre tap of a convolution that divides by P after its sum: out[comp][e] = mask[e] * [P]_{q_e} * ct[comp][e]
+// on the live q-limbs, zero on the special primes (out [2][E][N], mask [E][N], ct [2][level+1][N]).
+__global__ __launch_bounds__(PW_THREADS) void centre_ext_kernel(const u64* __restrict__ mask, const u64* __restrict__ ct,
+                                                                u64* __restrict__ out, const u64* __restrict__ negp,
+                                                                const ModConst* __restrict__ mc, u32 N, u32 level, u32 E) {
+    const u32 x = blockIdx.x * PW_THREADS + threadIdx.x;
+    if (x >= N) return;
+    const u32 e = blockIdx.y, comp = blockIdx.z;
+    u64 r = 0;
+    if (e <= level) {
+        const ModConst m = mc[e];
+        const u64 pm = mulmod_barrett(m.q - negp[e], mask[(size_t)e * N + x], m);
+        r = mulmod_barrett(pm, ct[((size_t)comp * (level + 1) + e) * N + x], m);
+    }
+    out[((size_t)comp * E + e) * N + x] = r;
+}
+
+hipError_t launch_centre_ext(const ckks_ctx* c, u32 level, const u64* mask, const u64* ct, u64* out, hipStream_t st) {
+    const u32 E = c->ext_limbs(level);
+    const u64* negp = c->d_moddown + 2 * c->k_pad + (size_t)c->k_pad * c->num_q + 2 * c->num_q;
+    dim3 grid((c->N + PW_THREADS - 1) / PW_THREADS, E, 2);
+    ProfScope ps__(c, K_MASK_MUL, st, 8.0 * c->N * (3.0 * (level + 1.0) + 2.0 * E), 4.0 * c->N * (level + 1.0));
+    hipLaunchKernelGGL(centre_ext_kernel, grid, dim3(PW_THREADS), 0, st, mask, ct, out, negp, c->d_mc, c->N, level, E);
+    return hipGetLastError();
+}
+
 // acc[o][comp][i][x] = sum_k w_res[o][k][i] * xs[k][comp][i][x]  mod q_i: the sum over (input
 // channel, tap) of Eq. 11 with the integer weight factored out of the plaintext.  Each thread keeps
 // WS_OUT_TILE output channels' 128-bit sums so that every xs element is loaded once per tile.
 #define WS_OUT_TILE 4
 __global__ __launch_bounds__(PW_THREADS) void weighted_sum_kernel(const u64* __restrict__ xs, const u64* __restrict__ w_res,
                                                                   u64* __restrict__ acc, const ModConst* __restrict__ mc, u32 N,
-                                                                  u32 level, u32 n_terms, u32 c_out, u32 lazy_terms) {
+                                                                  u32 level, u32 L1, u32 num_q, u32 n_terms, u32 c_out, u32 lazy_terms) {
     const u32 x = blockIdx.x * PW_THREADS + threadIdx.x;
     if (x >= N) return;
-    const u32 L1 = level + 1;
     const u32 i = blockIdx.y % L1, comp = blockIdx.y / L1;
     const u32 o0 = blockIdx.z * WS_OUT_TILE;
-    const ModConst m = mc[i];
+    const ModConst m = mc[i <= level ? i : num_q + (i - level - 1)];
     const size_t ct_stride = (size_t)2 * L1 * N;
     const size_t off = ((size_t)comp * L1 + i) * N + x;
     U128 s[WS_OUT_TILE];
@@ -224,7 +249,8 @@ __global__ __launch_bounds__(PW_THREADS) void transpose_weights_kernel(const u64
 
 __global__ __launch_bounds__(PW_THREADS) void weighted_sum50_kernel(const u64* __restrict__ xs, const u64* __restrict__ wt,
                                                                     u64* __restrict__ acc, const ModConst* __restrict__ mc, u32 N,
-                                                                    u32 level, u32 n_terms, u32 c_out, u32 co16, u32 n_xblocks) {
+                                                                    u32 level, u32 L1, u32 num_q, u32 n_terms, u32 c_out, u32 co16,
+                                                                    u32 n_xblocks) {
     const u32 n_ot = co16 / WS50_OUT_TILE;
     u32 xb, ot;
     if ((n_xblocks & 7u) == 0) {  // id = ((xb / 8) * n_ot + ot) * 8 + xb % 8
@@ -237,7 +263,6 @@ __global__ __launch_bounds__(PW_THREADS) void weighted_sum50_kernel(const u64* _
     }
     const u32 x = xb * PW_THREADS + threadIdx.x;
     if (x >= N) return;
-    const u32 L1 = level + 1;
     const u32 i = blockIdx.y % L1, comp = blockIdx.y / L1;
     const u32 o0 = ot * WS50_OUT_TILE;
     const size_t ct_stride = (size_t)2 * L1 * N;
@@ -255,36 +280,41 @@ __global__ __launch_bounds__(PW_THREADS) void weighted_sum50_kernel(const u64* _
 #pragma unroll
         for (u32 t = 0; t < WS50_OUT_TILE; t++) acc50_mad(s[t], v, split50(wv[t]));
     }
-    const ModConst m = mc[i];
+    const ModConst m = mc[i <= level ? i : num_q + (i - level - 1)];
 #pragma unroll
     for (u32 t = 0; t < WS50_OUT_TILE; t++)
         if (o0 + t < c_out) acc[(o0 + t) * ct_stride + off] = barrett_reduce(acc50_value(s[t]), m);
 }
 
-size_t weighted_sum_scratch_elems(const ckks_ctx* c, u32 level, u32 n_terms, u32 c_out) {
+size_t weighted_sum_scratch_elems(const ckks_ctx* c, u32 n_limbs, u32 n_terms, u32 c_out) {
     if (!(c->small_q && n_terms <= ACC50_MAX_TERMS)) return 0;
     const size_t co16 = (c_out + WS50_OUT_TILE - 1) / WS50_OUT_TILE * WS50_OUT_TILE;
-    return (size_t)(level + 1) * n_terms * co16;
+    return (size_t)n_limbs * n_terms * co16;
 }
 
+// xs [n_terms][2][nl][N], w_res [c_out][n_terms][nl], acc [c_out][2][nl][N]; nl = level+1 (the live q-limbs) or,
+// with `extended`, level+1+num_p (the extended basis: positions above `level` are the special primes).
 // scratch: weighted_sum_scratch_elems() words (may be null when that is 0)
-hipError_t launch_weighted_sum(const ckks_ctx* c, u32 level, const u64* xs, u32 n_terms, const u64* w_res, u32 c_out, u64* acc,
-                               u64* scratch, hipStream_t st) {
+hipError_t launch_weighted_sum(const ckks_ctx* c, u32 level, bool extended, const u64* xs, u32 n_terms, const u64* w_res, u32 c_out,
+                               u64* acc, u64* scratch, hipStream_t st) {
+    const u32 L1 = extended ? c->ext_limbs(level) : level + 1;
+    const double bytes = 16.0 * c->N * L1 * ((double)n_terms + c_out), ops = 2.0 * c->N * L1 * n_terms * c_out;
     if (c->small_q && n_terms <= ACC50_MAX_TERMS) {
-        const u32 co16 = (c_out + WS50_OUT_TILE - 1) / WS50_OUT_TILE * WS50_OUT_TILE, L1 = level + 1;
+        const u32 co16 = (c_out + WS50_OUT_TILE - 1) / WS50_OUT_TILE * WS50_OUT_TILE;
         const size_t wt_elems = (size_t)L1 * n_terms * co16;
         hipLaunchKernelGGL(transpose_weights_kernel, dim3((u32)((wt_elems + PW_THREADS - 1) / PW_THREADS)), dim3(PW_THREADS), 0, st,
                            w_res, scratch, c_out, co16, n_terms, L1);
         const u32 n_xblocks = (c->N + PW_THREADS - 1) / PW_THREADS;
         dim3 grid50(n_xblocks * (co16 / WS50_OUT_TILE), 2 * L1);
-        ProfScope ps__(c, K_WEIGHTED_SUM, st, 16.0 * c->N * (level + 1.0) * ((double)n_terms + c_out), 2.0 * c->N * (level + 1.0) * n_terms * c_out);
-        hipLaunchKernelGGL(weighted_sum50_kernel, grid50, dim3(PW_THREADS), 0, st, xs, scratch, acc, c->d_mc, c->N, level, n_terms, c_out,
-                           co16, n_xblocks);
+        ProfScope ps__(c, K_WEIGHTED_SUM, st, bytes, ops);
+        hipLaunchKernelGGL(weighted_sum50_kernel, grid50, dim3(PW_THREADS), 0, st, xs, scratch, acc, c->d_mc, c->N, level, L1, c->num_q,
+                           n_terms, c_out, co16, n_xblocks);
         return hipGetLastError();
     }
-    dim3 grid((c->N + PW_THREADS - 1) / PW_THREADS, 2 * (level + 1), (c_out + WS_OUT_TILE - 1) / WS_OUT_TILE);
-    { ProfScope ps__(c, K_WEIGHTED_SUM, st, 16.0 * c->N * (level + 1.0) * ((double)n_terms + c_out), 2.0 * c->N * (level + 1.0) * n_terms * c_out); hipLaunchKernelGGL(weighted_sum_kernel, grid, dim3(PW_THREADS), 0, st, xs, w_res, acc, c->d_mc, c->N, level, n_terms, c_out,
-                       c->lazy_terms); }
+    dim3 grid((c->N + PW_THREADS - 1) / PW_THREADS, 2 * L1, (c_out + WS_OUT_TILE - 1) / WS_OUT_TILE);
+    ProfScope ps__(c, K_WEIGHTED_SUM, st, bytes, ops);
+    hipLaunchKernelGGL(weighted_sum_kernel, grid, dim3(PW_THREADS), 0, st, xs, w_res, acc, c->d_mc, c->N, level, L1, c->num_q, n_terms,
+                       c_out, c->lazy_terms);
     return hipGetLastError();
 }
 

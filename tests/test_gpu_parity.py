@@ -133,7 +133,7 @@ def test_ctct_mul_relin_matches_oracle(ks_setup, level):
 
 
 # ----------------------------------------------------------------------------------- convolution
-def conv_case(name, level=None, bits=50, four_keys=False):
+def conv_case(name, level=None, bits=50, four_keys=False, deferred=False):
     wl = CONFIGS[name]
     p = make_params(wl.log_n, wl.num_q, wl.num_p, wl.dnum, bits=bits)
     orc, ctx = both(p)
@@ -145,12 +145,16 @@ def conv_case(name, level=None, bits=50, four_keys=False):
     cts = [orc.encrypt(orc.pack_channel(img, c), scale, level, s_ntt, 110 + c) for c in range(wl.c_in)]
     offs = conv_tap_offsets(wl.width)
     keys = {off: orc.gen_rotation_key(s, s_ntt, off, 200 + i) for i, off in enumerate(offs) if off}
-    masks, w_int = orc.conv_operands(w, wl.height, wl.width, wl.batch, level, 2.0 ** 28, p.moduli[level] / 2.0 ** 28)
+    operands = orc.conv_operands_ext if deferred else orc.conv_operands
+    masks, w_int = operands(w, wl.height, wl.width, wl.batch, level, 2.0 ** 28, p.moduli[level] / 2.0 ** 28)
+    w_moduli = [p.moduli[t] for t in orc.ext_moduli_idx(level)] if deferred else p.moduli
+    mode = hx.HE_CONV_DEFERRED_MODDOWN if deferred else (hx.HE_CONV_ALIGN_FOUR_KEYS if four_keys else hx.HE_CONV_ALIGN_DIRECT)
     if four_keys:                                 # only the keys of -1, +1, -W, +W exist
         keys = {off: k for off, k in keys.items() if off in (-1, 1, -wl.width, wl.width)}
     dkeys = [hx.ckks_key_load(ctx, hx.from_host(keys[off]), hx.ckks_galois_element(ctx, off)) if off in keys else None for off in offs]
     outs = hx.he_conv_batched(ctx, wl.height, wl.width, wl.batch, level, [hx.from_host(c) for c in cts], dkeys,
-                              hx.from_host(masks), hx.from_host(w_residues(w_int, p.moduli, level)), wl.c_out, four_keys=four_keys)
+                              hx.from_host(masks), hx.from_host(w_residues(w_int, w_moduli, len(w_moduli) - 1 if deferred else level)),
+                              wl.c_out, alignment=mode)
     return wl, p, orc, level, s_ntt, img, w, scale, cts, keys, masks, w_int, [hx.to_host(o) for o in outs]
 
 
@@ -183,6 +187,35 @@ def test_he_conv_four_key_alignment_matches_oracle(name, level, bits):
         assert np.abs(dec - ref[:, o]).max() < 1e-4
 
 
+@pytest.mark.parametrize("name,level,bits", [("cfg1_single_conv", None, 50), ("small_conv", None, 50), ("small_conv", 2, 50),
+                                             ("small_conv", 3, 56)])
+def test_he_conv_deferred_moddown_matches_oracle(name, level, bits):
+    """One division by P per output channel, after the sum on the extended basis: same residues as the
+    oracle's deferred schedule, same slots as the float64 convolution."""
+    wl, p, orc, level, s_ntt, img, w, scale, cts, keys, masks, w_int, outs = conv_case(name, level, bits, deferred=True)
+    want = orc.he_conv_deferred(cts, level, wl.width, keys, masks, w_int)
+    ref = conv2d_reference(img, w)
+    for o in range(wl.c_out):
+        assert np.array_equal(outs[o], want[o]), f"output channel {o}"
+        dec = orc.unpack_channel(orc.decrypt(outs[o], level - 1, s_ntt, scale), wl.batch, wl.height, wl.width)
+        assert np.abs(dec - ref[:, o]).max() < 1e-4
+
+
+def test_he_conv_deferred_needs_extended_operands():
+    wl = CONFIGS["cfg1_single_conv"]
+    p = wl.params()
+    orc, ctx = both(p)
+    level = p.num_q - 1
+    ct = hx.from_host(rand_ct(np.random.default_rng(2), p.moduli, level, orc.N))
+    with pytest.raises(ValueError):          # masks on the q-limbs only
+        hx.he_conv_batched(ctx, wl.height, wl.width, wl.batch, level, [ct], [None] * 9, hx.empty(9, level + 1, orc.N),
+                           hx.empty(1, 1, 9, level + 1), 1, alignment=hx.HE_CONV_DEFERRED_MODDOWN)
+    with pytest.raises(hx.CkksError) as e:
+        hx.he_conv_batched(ctx, wl.height, wl.width, wl.batch, level, [ct], [None] * 9, hx.empty(9, level + 1, orc.N),
+                           hx.empty(1, 1, 9, level + 1), 1, alignment=7)
+    assert e.value.code == hx.binding.CKKS_ERR_INVALID_ARG
+
+
 def test_he_conv_four_keys_rejects_a_missing_key():
     wl = CONFIGS["cfg1_single_conv"]
     p = wl.params()
@@ -191,7 +224,7 @@ def test_he_conv_four_keys_rejects_a_missing_key():
     ct = hx.from_host(rand_ct(np.random.default_rng(2), p.moduli, level, orc.N))
     with pytest.raises(hx.CkksError) as e:
         hx.he_conv_batched(ctx, wl.height, wl.width, wl.batch, level, [ct], [None] * 9, hx.empty(9, level + 1, orc.N),
-                           hx.empty(1, 1, 9, level + 1), 1, four_keys=True)
+                           hx.empty(1, 1, 9, level + 1), 1, alignment=hx.HE_CONV_ALIGN_FOUR_KEYS)
     assert e.value.code == hx.binding.CKKS_ERR_NO_KEY
 
 
