@@ -55,6 +55,9 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="cfg5_resnet20_stage3")
+    ap.add_argument("--alignment", default="deferred", choices=["direct", "four_keys", "deferred"],
+                    help="convolution schedule: eight hoisted rotations with one ModDown each (direct), the paper's four-key "
+                         "two-stage alignment, or one ModDown per output channel after the sum (deferred, the default)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--no-kernel-timing", action="store_true", help="skip the per-kernel event pass")
     ap.add_argument("--no-microbench", action="store_true", help="skip the rotation and NTT microbenchmarks")
@@ -124,19 +127,23 @@ def main():
     keys = [hx.ckks_key_load(ctx, hx.from_host(uniform_residues((params.dnum, 2, M, N), q, "rk%d" % t)),
                              hx.ckks_galois_element(ctx, off)) if off else None for t, off in enumerate(offs)]
     rlk = hx.ckks_key_load(ctx, hx.from_host(uniform_residues((params.dnum, 2, M, N), q, "rlk")), 0)
-    masks = hx.from_host(uniform_residues((9, level + 1, N), q[:level + 1], "masks"))
-    w_res = hx.from_host(uniform_residues((wl.c_out * wl.c_in * 9, level + 1, 1), q[:level + 1], "w").reshape(wl.c_out, wl.c_in, 9, level + 1))
+    mode = {"direct": hx.HE_CONV_ALIGN_DIRECT, "four_keys": hx.HE_CONV_ALIGN_FOUR_KEYS, "deferred": hx.HE_CONV_DEFERRED_MODDOWN}[args.alignment]
+    # operands of the multiply-accumulate live on the extended basis (q_0..q_level, p_0..) in the deferred schedule
+    q_mac = (q[:level + 1] + q[params.num_q:]) if args.alignment == "deferred" else q[:level + 1]
+    masks = hx.from_host(uniform_residues((9, len(q_mac), N), q_mac, "masks"))
+    w_res = hx.from_host(uniform_residues((wl.c_out * wl.c_in * 9, len(q_mac), 1), q_mac, "w").reshape(wl.c_out, wl.c_in, 9, len(q_mac)))
     conv_out = [hx.empty(2, level, N) for _ in range(wl.c_out)]
     act_out = [hx.empty(2, level - 4, N) for _ in range(wl.c_out)]
     k_act = (3 << 40, -(5 << 40), 7 << 40, -(9 << 40))
-    ws_bytes = max(hx.he_conv_workspace_bytes(ctx, wl.c_in, wl.c_out, wl.height, wl.width, wl.batch, level),
+    ws_bytes = max(hx.he_conv_workspace_bytes(ctx, wl.c_in, wl.c_out, wl.height, wl.width, wl.batch, level, mode),
                    hx.ckks_workspace_bytes(ctx, hx.binding.CKKS_OP_POLY_ACT, level - 1, wl.c_out))
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
     torch.cuda.synchronize()
     print("[bench] setup %.1f s, workspace %.2f GiB" % (time.perf_counter() - t_setup, ws_bytes / 2**30), file=sys.stderr, flush=True)
 
     def step():
-        hx.he_conv_batched(ctx, wl.height, wl.width, wl.batch, level, ins, keys, masks, w_res, wl.c_out, outs=conv_out, ws=ws)
+        hx.he_conv_batched(ctx, wl.height, wl.width, wl.batch, level, ins, keys, masks, w_res, wl.c_out, outs=conv_out, ws=ws,
+                           alignment=mode)
         hx.he_poly_act_deg7(ctx, conv_out, level - 1, k_act, rlk, outs=act_out, ws=ws)
 
     for _ in range(args.warmup):
@@ -161,7 +168,8 @@ def main():
         "dtype": "u64", "data": "synthetic",
         "config": {"workload": wl.name, "log_n": params.log_n, "limbs": params.num_q, "special_primes": params.num_p,
                    "dnum": params.dnum, "c_in": wl.c_in, "c_out": wl.c_out, "image": "%dx%d" % (wl.height, wl.width),
-                   "batch": wl.batch, "rotations_per_step": n_rot, "keyswitches_per_step": n_keyswitch},
+                   "batch": wl.batch, "rotations_per_step": n_rot, "keyswitches_per_step": n_keyswitch,
+                   "conv_schedule": args.alignment},
     }
 
     # per-kernel event timing over one more step (every launch bracketed on its own stream)

@@ -155,6 +155,11 @@ hipError_t launch_centre_ext(const ckks_ctx* c, u32 level, const u64* mask, cons
 size_t weighted_sum_scratch_elems(const ckks_ctx* c, u32 n_limbs, u32 n_terms, u32 c_out);
 hipError_t launch_weighted_sum(const ckks_ctx* c, u32 level, bool extended, const u64* xs, u32 n_terms, const u64* w_res, u32 c_out,
                                u64* acc, u64* scratch, hipStream_t st);
+// wsum_mfma.hip
+bool wsum_mfma_applies(const ckks_ctx* c, u32 n_terms);
+size_t wsum_mfma_scratch_elems(u32 n_limbs, u32 n_terms, u32 c_out);
+hipError_t launch_wsum_mfma(const ckks_ctx* c, u32 level, u32 nl, const u64* xs, u32 n_terms, const u64* w_res, u32 c_out, u64* acc,
+                            u64* scratch, hipStream_t st);
 hipError_t launch_lincomb2(const ckks_ctx* c, u32 level, const PtrList8& a, size_t a_cstride, const u64* ka, const PtrList8& b,
                            size_t b_cstride, const u64* kb, const u64* add, size_t add_bstride, u64* out, size_t out_bstride, u32 n,
                            hipStream_t st);

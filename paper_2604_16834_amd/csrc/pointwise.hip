@@ -197,7 +197,8 @@ hipError_t launch_centre_ext(const ckks_ctx* c, u32 level, const u64* mask, cons
 }
 
 // acc[o][comp][i][x] = sum_k w_res[o][k][i] * xs[k][comp][i][x]  mod q_i: the sum over (input
-// channel, tap) of Eq. 11 with the integer weight factored out of the plaintext.  Each thread keeps
+// channel, tap) of Eq. 11 with the integer weight factored out of the plaintext.  This is the kernel
+// for moduli above 2^50 (the matrix-core kernel in wsum_mfma.hip takes the others): each thread keeps
 // WS_OUT_TILE output channels' 128-bit sums so that every xs element is loaded once per tile.
 #define WS_OUT_TILE 4
 __global__ __launch_bounds__(PW_THREADS) void weighted_sum_kernel(const u64* __restrict__ xs, const u64* __restrict__ w_res,
@@ -230,66 +231,9 @@ __global__ __launch_bounds__(PW_THREADS) void weighted_sum_kernel(const u64* __r
         if (o0 + t < c_out) acc[(o0 + t) * ct_stride + off] = barrett_reduce(s[t], m);
 }
 
-// The same sum for moduli below 2^50 (n_terms <= 4096): three multiply-adds per product into plain
-// 64-bit sums, 16 output channels per thread.  The weights are first transposed to
-// wt[limb][term][C_out rounded up to 16] so that the 16 weights of one term are one aligned 128-byte
-// run that the whole wavefront fetches with two wide scalar loads.  Workgroups that read the same xs
-// data (same coefficients, different output tiles) get ids that are 8 apart, so they run at the
-// same time on the same XCD and all but the first are served by that XCD's L2.
-#define WS50_OUT_TILE 16
-__global__ __launch_bounds__(PW_THREADS) void transpose_weights_kernel(const u64* __restrict__ w_res, u64* __restrict__ wt, u32 c_out,
-                                                                       u32 co16, u32 n_terms, u32 L1) {
-    const size_t idx = (size_t)blockIdx.x * PW_THREADS + threadIdx.x;
-    if (idx >= (size_t)L1 * n_terms * co16) return;
-    const u32 o = (u32)(idx % co16);
-    const size_t r = idx / co16;
-    const u32 k = (u32)(r % n_terms), i = (u32)(r / n_terms);
-    wt[idx] = o < c_out ? w_res[((size_t)o * n_terms + k) * L1 + i] : 0;
-}
-
-__global__ __launch_bounds__(PW_THREADS) void weighted_sum50_kernel(const u64* __restrict__ xs, const u64* __restrict__ wt,
-                                                                    u64* __restrict__ acc, const ModConst* __restrict__ mc, u32 N,
-                                                                    u32 level, u32 L1, u32 num_q, u32 n_terms, u32 c_out, u32 co16,
-                                                                    u32 n_xblocks) {
-    const u32 n_ot = co16 / WS50_OUT_TILE;
-    u32 xb, ot;
-    if ((n_xblocks & 7u) == 0) {  // id = ((xb / 8) * n_ot + ot) * 8 + xb % 8
-        const u32 rest = blockIdx.x >> 3;
-        ot = rest % n_ot;
-        xb = (rest / n_ot) * 8 + (blockIdx.x & 7u);
-    } else {
-        ot = blockIdx.x % n_ot;
-        xb = blockIdx.x / n_ot;
-    }
-    const u32 x = xb * PW_THREADS + threadIdx.x;
-    if (x >= N) return;
-    const u32 i = blockIdx.y % L1, comp = blockIdx.y / L1;
-    const u32 o0 = ot * WS50_OUT_TILE;
-    const size_t ct_stride = (size_t)2 * L1 * N;
-    const size_t off = ((size_t)comp * L1 + i) * N + x;
-    Acc50 s[WS50_OUT_TILE];
-#pragma unroll
-    for (u32 t = 0; t < WS50_OUT_TILE; t++) s[t] = {0, 0, 0};
-    const u64* wrow = (const u64*)__builtin_assume_aligned(wt + (size_t)i * n_terms * co16 + o0, 128);
-    for (u32 k = 0; k < n_terms; k++) {
-        const Split50 v = split50(xs[k * ct_stride + off]);
-        const u64* wk = (const u64*)__builtin_assume_aligned(wrow + (size_t)k * co16, 128);
-        u64 wv[WS50_OUT_TILE];
-#pragma unroll
-        for (u32 t = 0; t < WS50_OUT_TILE; t++) wv[t] = wk[t];
-#pragma unroll
-        for (u32 t = 0; t < WS50_OUT_TILE; t++) acc50_mad(s[t], v, split50(wv[t]));
-    }
-    const ModConst m = mc[i <= level ? i : num_q + (i - level - 1)];
-#pragma unroll
-    for (u32 t = 0; t < WS50_OUT_TILE; t++)
-        if (o0 + t < c_out) acc[(o0 + t) * ct_stride + off] = barrett_reduce(acc50_value(s[t]), m);
-}
-
 size_t weighted_sum_scratch_elems(const ckks_ctx* c, u32 n_limbs, u32 n_terms, u32 c_out) {
-    if (!(c->small_q && n_terms <= ACC50_MAX_TERMS)) return 0;
-    const size_t co16 = (c_out + WS50_OUT_TILE - 1) / WS50_OUT_TILE * WS50_OUT_TILE;
-    return (size_t)n_limbs * n_terms * co16;
+    if (wsum_mfma_applies(c, n_terms)) return wsum_mfma_scratch_elems(n_limbs, n_terms, c_out);
+    return 0;
 }
 
 // xs [n_terms][2][nl][N], w_res [c_out][n_terms][nl], acc [c_out][2][nl][N]; nl = level+1 (the live q-limbs) or,
@@ -299,17 +243,9 @@ hipError_t launch_weighted_sum(const ckks_ctx* c, u32 level, bool extended, cons
                                u64* acc, u64* scratch, hipStream_t st) {
     const u32 L1 = extended ? c->ext_limbs(level) : level + 1;
     const double bytes = 16.0 * c->N * L1 * ((double)n_terms + c_out), ops = 2.0 * c->N * L1 * n_terms * c_out;
-    if (c->small_q && n_terms <= ACC50_MAX_TERMS) {
-        const u32 co16 = (c_out + WS50_OUT_TILE - 1) / WS50_OUT_TILE * WS50_OUT_TILE;
-        const size_t wt_elems = (size_t)L1 * n_terms * co16;
-        hipLaunchKernelGGL(transpose_weights_kernel, dim3((u32)((wt_elems + PW_THREADS - 1) / PW_THREADS)), dim3(PW_THREADS), 0, st,
-                           w_res, scratch, c_out, co16, n_terms, L1);
-        const u32 n_xblocks = (c->N + PW_THREADS - 1) / PW_THREADS;
-        dim3 grid50(n_xblocks * (co16 / WS50_OUT_TILE), 2 * L1);
+    if (wsum_mfma_applies(c, n_terms)) {  // moduli below 2^50: exact 8-bit digit products on the matrix cores
         ProfScope ps__(c, K_WEIGHTED_SUM, st, bytes, ops);
-        hipLaunchKernelGGL(weighted_sum50_kernel, grid50, dim3(PW_THREADS), 0, st, xs, scratch, acc, c->d_mc, c->N, level, L1, c->num_q,
-                           n_terms, c_out, co16, n_xblocks);
-        return hipGetLastError();
+        return launch_wsum_mfma(c, level, L1, xs, n_terms, w_res, c_out, acc, scratch, st);
     }
     dim3 grid((c->N + PW_THREADS - 1) / PW_THREADS, 2 * L1, (c_out + WS_OUT_TILE - 1) / WS_OUT_TILE);
     ProfScope ps__(c, K_WEIGHTED_SUM, st, bytes, ops);

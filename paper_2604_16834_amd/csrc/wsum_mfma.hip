@@ -1,0 +1,278 @@
+// The multiply-accumulate over (input channel, tap) of the batched convolution (Methodology,
+// "Convolution Evaluation", Eq. 11 and the rotation-free channel sum after it) on the matrix cores.
+//
+// With the integer weight factored out of the plaintext the layer's sum is, for every limb e, a dense
+// modular matrix product
+//     acc[o][x] = sum_k W_e[o][k] * X_e[k][x]  mod q_e,      o < C_out, k < 9*C_in, x < 2N,
+// of a small weight matrix with the aligned, masked ciphertexts.  Residues below 2^50 are written in
+// seven signed base-256 digits (v + bias with bias = 0x80 in each of the seven low bytes has the
+// digits + 128 as its bytes, so two 64-bit operations give all seven); the 49 digit-by-digit products
+// are exact 8-bit integer matrix products with 32-bit sums (v_mfma_i32_32x32x32_i8, the shape that
+// runs at the full 8-bit rate: measured 4.3 POP/s against 2.5 for the 16x16x64 shape), summed by
+// diagonal (digit positions adding up to s) in 13 accumulators; sum_s D_s 2^(8s) is the exact integer
+// sum of products, reduced once with Barrett.  Nothing is approximated: the result is the same
+// canonical residue the scalar kernels give.
+//
+// One 256-thread workgroup = 64 columns x of one (component, limb) times 64 output channels.  Wave w
+// owns output tile w&1 (32 channels) and column tile w>>1 (32 columns): every lane loads its own 32 X
+// values of a 64-term block of k straight from HBM (32 lanes = one 256-byte run per term), splits them
+// into digits and transposes bytes in registers (v_perm_b32) into the B operands.  The digit planes
+// of the weights are prepared once per call in the A-operand lane layout and staged through LDS
+// (double-buffered) so that the waves share them.  X streams from HBM exactly once.
+#include "ctx.h"
+
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v16i __attribute__((ext_vector_type(16)));
+
+#define WM_THREADS 256
+#define WM_DIGITS 7
+#define WM_DIAGS (2 * WM_DIGITS - 1)
+#define WM_BIAS 0x0080808080808080ull
+#define WM_OT_PER_WG 2                                  // output tiles of 32 channels per workgroup
+#define WM_A_STAGE (WM_OT_PER_WG * WM_DIGITS * 2 * 64)  // uint4 words of one 64-term block of weights (28 KiB)
+#define WM_A_PER_THREAD (WM_A_STAGE / WM_THREADS)       // 7
+
+// bytes 0..6 = the seven signed base-256 digits of v < 2^55 (two's complement bytes)
+__host__ __device__ __forceinline__ u64 signed_digits(u64 v) { return (v + WM_BIAS) ^ WM_BIAS; }
+
+// ---- weights: w_res [c_out][n_terms][nl] -> digit planes in A-operand layout ---------------------
+// wa[(((e*KB + kb)*OT + ot)*7 + dw)*2 + ks][lane] = 16 bytes: digit dw of
+//   W[32*ot + lane%32][64*kb + 32*ks + 16*(lane/32) + j], j < 16
+// (zero beyond c_out / n_terms; OT = number of 32-channel tiles rounded up to a multiple of 2)
+__global__ __launch_bounds__(WM_THREADS) void wsum_prep_kernel(const u64* __restrict__ w_res, uint4* __restrict__ wa, u32 c_out,
+                                                               u32 n_terms, u32 nl, u32 KB, u32 OT) {
+    const size_t idx = (size_t)blockIdx.x * WM_THREADS + threadIdx.x;
+    if (idx >= (size_t)nl * KB * OT * WM_DIGITS * 2 * 64) return;
+    const u32 lane = (u32)(idx & 63);
+    size_t r = idx >> 6;
+    const u32 ks = (u32)(r & 1);
+    r >>= 1;
+    const u32 dw = (u32)(r % WM_DIGITS);
+    r /= WM_DIGITS;
+    const u32 ot = (u32)(r % OT);
+    r /= OT;
+    const u32 kb = (u32)(r % KB), e = (u32)(r / KB);
+    const u32 o = 32 * ot + (lane & 31), k0 = 64 * kb + 32 * ks + 16 * (lane >> 5);
+    u32 words[4];
+#pragma unroll
+    for (u32 m = 0; m < 4; m++) {
+        u32 wv = 0;
+#pragma unroll
+        for (u32 j = 0; j < 4; j++) {
+            const u32 k = k0 + 4 * m + j;
+            const u64 v = (o < c_out && k < n_terms) ? w_res[((size_t)o * n_terms + k) * nl + e] : 0;
+            wv |= (u32)((signed_digits(v) >> (8 * dw)) & 0xffu) << (8 * j);
+        }
+        words[m] = wv;
+    }
+    wa[idx] = make_uint4(words[0], words[1], words[2], words[3]);
+}
+
+// {a.b[i], b.b[i], c.b[i], d.b[i]} for i = 0..3 from four dwords (a 4x4 byte transpose)
+__device__ __forceinline__ void transpose4(u32 a, u32 b, u32 c, u32 d, u32& o0, u32& o1, u32& o2, u32& o3) {
+    const u32 ab_lo = __builtin_amdgcn_perm(b, a, 0x05010400u);  // a0 b0 a1 b1
+    const u32 ab_hi = __builtin_amdgcn_perm(b, a, 0x07030602u);  // a2 b2 a3 b3
+    const u32 cd_lo = __builtin_amdgcn_perm(d, c, 0x05010400u);
+    const u32 cd_hi = __builtin_amdgcn_perm(d, c, 0x07030602u);
+    o0 = __builtin_amdgcn_perm(cd_lo, ab_lo, 0x05040100u);       // a0 b0 c0 d0
+    o1 = __builtin_amdgcn_perm(cd_lo, ab_lo, 0x07060302u);
+    o2 = __builtin_amdgcn_perm(cd_hi, ab_hi, 0x05040100u);
+    o3 = __builtin_amdgcn_perm(cd_hi, ab_hi, 0x07060302u);
+}
+
+// Digits of 16 values (one per term) -> the seven 16-byte B-operand words of this lane.
+__device__ __forceinline__ void digits_to_b(const u64* v, uint4* bw) {
+    u32 w[7][4];
+#pragma unroll
+    for (u32 m = 0; m < 4; m++) {
+        const u64 s0 = signed_digits(v[4 * m]), s1 = signed_digits(v[4 * m + 1]), s2 = signed_digits(v[4 * m + 2]),
+                  s3 = signed_digits(v[4 * m + 3]);
+        u32 unused;
+        transpose4((u32)s0, (u32)s1, (u32)s2, (u32)s3, w[0][m], w[1][m], w[2][m], w[3][m]);
+        transpose4((u32)(s0 >> 32), (u32)(s1 >> 32), (u32)(s2 >> 32), (u32)(s3 >> 32), w[4][m], w[5][m], w[6][m], unused);
+    }
+#pragma unroll
+    for (u32 dx = 0; dx < 7; dx++) bw[dx] = make_uint4(w[dx][0], w[dx][1], w[dx][2], w[dx][3]);
+}
+
+// xs [n_terms][2][nl][N], wa as above, acc [c_out][2][nl][N];  grid = (ceil(N/64), 2*nl, OT/2).
+// RAGGED: n_terms is not a multiple of 64 or N is not a multiple of 64 (addresses are clamped and
+// the values behind them masked to zero); the regular case carries none of that.
+//
+// Per 64-term block kb the workgroup needs 28 KiB of weight digits (A operands, shared) and the
+// digits of its 64 x 64 values of X (B operands; thread (wave, lane) converts 16 of them: column
+// tile wave>>1, terms 32*(wave&1) + 16*(lane>>5) + j, and shares them through LDS with the wave that
+// owns the other output tile).  Both live in double-buffered LDS.  Iteration kb: store the weights of
+// block kb+1 (requested an iteration ago), request X of block kb+2 and the weights of block kb+2,
+// then run the 98 matrix instructions of block kb out of LDS while the vector ALU turns X of block
+// kb+1 (requested an iteration ago) into digits for the other LDS buffer.
+template <bool RAGGED>
+__global__ __launch_bounds__(WM_THREADS) void wsum_mfma_kernel(const u64* __restrict__ xs, const uint4* __restrict__ wa,
+                                                               u64* __restrict__ acc, const ModConst* __restrict__ mc, u32 N,
+                                                               u32 level, u32 nl, u32 num_q, u32 n_terms, u32 c_out, u32 KB, u32 OT) {
+    __shared__ uint4 lds_a[2][WM_A_STAGE];
+    __shared__ uint4 lds_b[2][WM_A_STAGE];  // [column tile 2][32-term step 2][digit 7][lane 64]
+    const u32 tid = threadIdx.x, lane = tid & 63;
+    const u32 wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const u32 g = lane >> 5;                 // which 16 terms of a 32-term step this lane holds
+    const u32 wt = wave & 1;                 // output tile this wave owns; also the 32-term step whose X it converts
+    const u32 xt = wave >> 1;                // column tile
+    const u32 x = blockIdx.x * 64 + xt * 32 + (lane & 31);
+    const u32 e = blockIdx.y % nl, comp = blockIdx.y / nl;
+    const u32 ot0 = blockIdx.z * WM_OT_PER_WG;
+    const size_t ct_stride = (size_t)2 * nl * N;
+    const size_t off = ((size_t)comp * nl + e) * N + x;
+    const bool x_ok = !RAGGED || x < N;
+
+    v16i d[WM_DIAGS];
+#pragma unroll
+    for (int s = 0; s < WM_DIAGS; s++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) d[s][r] = 0;
+
+    // term 64*kb + 32*wt + j + 16*g of column x: a wave-uniform row pointer plus a 32-bit lane offset
+    const u64* xbase = xs + ((size_t)comp * nl + e) * N + (size_t)(32 * wt) * ct_stride;
+    const u32 lane_off = (u32)(16 * g * ct_stride) + (x_ok ? x : N - 1);
+    const uint4* wsrc = wa + ((size_t)e * KB * OT + ot0) * (WM_DIGITS * 2 * 64) + tid;  // block kb: + kb * wstep
+    const size_t wstep = (size_t)OT * (WM_DIGITS * 2 * 64);
+    u64 raw0[16], raw1[16];
+    uint4 ap0, ap1, ap2, ap3, ap4, ap5, ap6;  // named, not an array: they live across the loop's back edge in registers
+#define WM_LOAD_X(RAW, KBLK)                                                                          \
+    _Pragma("unroll") for (u32 j = 0; j < 16; j++) {                                                  \
+        if (RAGGED) {                                                                                 \
+            const u32 k = 64 * (KBLK) + 32 * wt + 16 * g + j;                                         \
+            RAW[j] = xs[(size_t)(k < n_terms ? k : n_terms - 1) * ct_stride + ((size_t)comp * nl + e) * N + (x_ok ? x : N - 1)]; \
+        } else {                                                                                      \
+            RAW[j] = (xbase + (size_t)(64 * (KBLK) + j) * ct_stride)[lane_off];                       \
+        }                                                                                             \
+    }
+#define WM_MASK_X(RAW, KBLK)                                                                          \
+    if (RAGGED) {                                                                                     \
+        _Pragma("unroll") for (u32 j = 0; j < 16; j++)                                                \
+            RAW[j] &= (x_ok && 64 * (KBLK) + 32 * wt + 16 * g + j < n_terms) ? ~0ull : 0ull;          \
+    }
+#define WM_A_EACH(OP) \
+    { OP(0, ap0) OP(1, ap1) OP(2, ap2) OP(3, ap3) OP(4, ap4) OP(5, ap5) OP(6, ap6) }
+#define WM_A_LD(I, V) V = wsrc[kblk__ * wstep + I * WM_THREADS];
+#define WM_A_ST(I, V) lds_a[buf__][tid + I * WM_THREADS] = V;
+#define WM_LOAD_A(KBLK) { const size_t kblk__ = (KBLK); WM_A_EACH(WM_A_LD) }
+#define WM_STORE_A(BUF) { const u32 buf__ = (BUF); WM_A_EACH(WM_A_ST) }
+#define WM_STORE_B(RAW, BUF)                                                                          \
+    {                                                                                                 \
+        uint4 bw__[7];                                                                                \
+        digits_to_b(RAW, bw__);                                                                       \
+        _Pragma("unroll") for (u32 dx = 0; dx < 7; dx++) lds_b[BUF][((xt * 2 + wt) * 7 + dx) * 64 + lane] = bw__[dx]; \
+    }
+// One iteration: RAW_NEW receives X of block kb+2, RAW_OLD holds X of block kb+1.
+#define WM_ITER(RAW_NEW, RAW_OLD)                                                                     \
+    {                                                                                                 \
+        const u32 cur = kb & 1;                                                                       \
+        __syncthreads(); /* blocks kb of both operands are in LDS[cur]; everyone is done with LDS[cur ^ 1] */ \
+        WM_STORE_A(cur ^ 1)                                                                           \
+        const u32 kx = kb + 2 < KB ? kb + 2 : KB - 1;                                                 \
+        WM_LOAD_X(RAW_NEW, kx)                                                                        \
+        WM_LOAD_A(kx)                                                                                 \
+        __builtin_amdgcn_sched_barrier(0);                                                            \
+        const uint4* la = &lds_a[cur][wt * (WM_DIGITS * 2 * 64) + lane];                              \
+        const uint4* lb = &lds_b[cur][xt * (2 * WM_DIGITS * 64) + lane];                              \
+        v4i b[WM_DIGITS][2];                                                                          \
+        _Pragma("unroll") for (u32 ks = 0; ks < 2; ks++)                                              \
+            _Pragma("unroll") for (u32 dx = 0; dx < WM_DIGITS; dx++) {                                \
+                const uint4 t = lb[(ks * WM_DIGITS + dx) * 64];                                       \
+                b[dx][ks] = (v4i){(int)t.x, (int)t.y, (int)t.z, (int)t.w};                            \
+            }                                                                                         \
+        uint4 av = la[0];                                                                             \
+        _Pragma("unroll") for (u32 i = 0; i < WM_DIGITS * 2; i++) {                                   \
+            const u32 dw = i >> 1, ks = i & 1;                                                        \
+            const v4i a = (v4i){(int)av.x, (int)av.y, (int)av.z, (int)av.w};                          \
+            if (i + 1 < WM_DIGITS * 2) av = la[(i + 1) * 64];                                         \
+            _Pragma("unroll") for (u32 dx = 0; dx < WM_DIGITS; dx++)                                  \
+                d[dx + dw] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[dx][ks], d[dx + dw], 0, 0, 0); \
+        }                                                                                             \
+        WM_MASK_X(RAW_OLD, kb + 1)                                                                    \
+        WM_STORE_B(RAW_OLD, cur ^ 1)                                                                  \
+        /* issue order: the 16 LDS reads that start the block, then per matrix instruction two vector */ \
+        /* instructions of the digit conversion, an LDS read every seven, the LDS writes last */        \
+        __builtin_amdgcn_sched_group_barrier(0x100, 16, 0);                                           \
+        _Pragma("unroll") for (u32 i = 0; i < WM_DIGITS * 2; i++) {                                   \
+            _Pragma("unroll") for (u32 q = 0; q < WM_DIGITS; q++) {                                   \
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                    \
+                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);                                    \
+            }                                                                                         \
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                        \
+        }                                                                                             \
+        __builtin_amdgcn_sched_group_barrier(0x200, 7, 0);                                            \
+        __builtin_amdgcn_sched_barrier(0);                                                            \
+    }
+
+    WM_LOAD_A(0)
+    WM_STORE_A(0)
+    WM_LOAD_X(raw0, 0)
+    WM_MASK_X(raw0, 0)
+    WM_STORE_B(raw0, 0)
+    WM_LOAD_A(KB > 1 ? 1 : 0)
+    WM_LOAD_X(raw1, KB > 1 ? 1 : 0)
+    for (u32 kb = 0; kb < KB; kb += 2) {
+        WM_ITER(raw0, raw1)
+        kb++;
+        if (kb < KB) WM_ITER(raw1, raw0)
+        kb--;
+    }
+#undef WM_LOAD_X
+#undef WM_MASK_X
+#undef WM_LOAD_A
+#undef WM_STORE_A
+#undef WM_STORE_B
+#undef WM_ITER
+#undef WM_A_EACH
+#undef WM_A_LD
+#undef WM_A_ST
+
+    // sum_s D_s 2^(8s): the exact, non-negative sum of products (below n_terms * 2^100), reduced once
+    if (!x_ok) return;
+    const ModConst m = mc[e <= level ? e : num_q + (e - level - 1)];
+#pragma unroll
+    for (u32 r = 0; r < 16; r++) {
+        const u32 o = 32 * (ot0 + wt) + 8 * (r >> 2) + 4 * g + (r & 3);
+        if (o >= c_out) continue;
+        // three diagonals per 64-bit word, then Horner in 128 bits with steps of 24 bits
+        long long T[5];
+#pragma unroll
+        for (u32 j = 0; j < 4; j++)
+            T[j] = (long long)d[3 * j][r] + (long long)d[3 * j + 1][r] * 256 + (long long)d[3 * j + 2][r] * 65536;
+        T[4] = (long long)d[12][r];
+        __int128 val = T[4];
+#pragma unroll
+        for (int j = 3; j >= 0; j--) val = val * (1 << 24) + T[j];
+        U128 u;
+        u.lo = (u64)val;
+        u.hi = (u64)(val >> 64);
+        acc[(size_t)o * ct_stride + off] = barrett_reduce(u, m);
+    }
+}
+
+bool wsum_mfma_applies(const ckks_ctx* c, u32 n_terms) { return c->small_q && n_terms <= c->lazy_terms && n_terms <= 4096; }
+
+// scratch words (u64) for the weight digit planes
+size_t wsum_mfma_scratch_elems(u32 n_limbs, u32 n_terms, u32 c_out) {
+    const size_t KB = (n_terms + 63) / 64, OT = (c_out + 63) / 64 * WM_OT_PER_WG;
+    return (size_t)n_limbs * KB * OT * WM_DIGITS * 2 * 64 * 2;  // 16 bytes per lane
+}
+
+hipError_t launch_wsum_mfma(const ckks_ctx* c, u32 level, u32 nl, const u64* xs, u32 n_terms, const u64* w_res, u32 c_out, u64* acc,
+                            u64* scratch, hipStream_t st) {
+    const u32 KB = (n_terms + 63) / 64, OT = (c_out + 63) / 64 * WM_OT_PER_WG;
+    const size_t prep = (size_t)nl * KB * OT * WM_DIGITS * 2 * 64;
+    hipLaunchKernelGGL(wsum_prep_kernel, dim3((u32)((prep + WM_THREADS - 1) / WM_THREADS)), dim3(WM_THREADS), 0, st, w_res,
+                       (uint4*)scratch, c_out, n_terms, nl, KB, OT);
+    dim3 grid((c->N + 63) / 64, 2 * nl, OT / WM_OT_PER_WG);
+    // the 32-bit lane offset of the regular kernel spans 16 terms: 16 * (2 * nl * N) words must fit
+    const bool ragged = (n_terms & 63) || (c->N & 63) || (size_t)16 * 2 * nl * c->N + c->N > 0xffffffffull;
+    if (ragged)
+        hipLaunchKernelGGL(wsum_mfma_kernel<true>, grid, dim3(WM_THREADS), 0, st, xs, (const uint4*)scratch, acc, c->d_mc, c->N, level,
+                           nl, c->num_q, n_terms, c_out, KB, OT);
+    else
+        hipLaunchKernelGGL(wsum_mfma_kernel<false>, grid, dim3(WM_THREADS), 0, st, xs, (const uint4*)scratch, acc, c->d_mc, c->N, level,
+                           nl, c->num_q, n_terms, c_out, KB, OT);
+    return hipGetLastError();
+}
