@@ -103,10 +103,11 @@ def test_cfg4_resnet20_stage1_conv():
 def test_cfg5_resnet20_stage3_block_slice():
     """64 -> 64 channels on 8x8 images, batch 512, 24 limbs + 8 special primes, then the degree-7
     activation on all 64 channels: the launch configuration bench.py times.  The oracle cannot
-    afford the 512 rotations, so: every conv output decrypted against the float64 convolution (1e-4)
-    and every activation output against the float64 polynomial (1e-3); limb-for-limb parity of the
-    activation on sampled channels (computed by the oracle from the GPU's conv output), and of the
-    whole conv on an 8 -> 3 channel slice of the same shape."""
+    afford the 512 rotations, so: every conv output (deferred-ModDown schedule, as timed) decrypted
+    against the float64 convolution (1e-4) and every activation output against the float64 polynomial
+    (1e-3); limb-for-limb parity of the activation on sampled channels (computed by the oracle from the
+    GPU's conv output), and of the whole conv, in the direct and in the deferred schedule, on an 8 -> 3
+    channel slice of the same shape."""
     wl = CONFIGS["cfg5_resnet20_stage3"]
     p = wl.params()
     orc, ctx = Oracle(p), hx.Context(p)
@@ -115,12 +116,17 @@ def test_cfg5_resnet20_stage3_block_slice():
     s, s_ntt, img, w, cts, offs, keys = _conv_inputs(wl, p, orc, level, 5000, weight_gain=0.2)
     rlk = orc.gen_relin_key(s_ntt, 5999)
     delta_pt = p.moduli[level] * 2.0 ** 10                 # conv output lands at scale 2^50
-    masks, w_int = orc.conv_operands(w, wl.height, wl.width, wl.batch, level, 2.0 ** 28, delta_pt / 2.0 ** 28)
+    # the schedule bench.py times: one division by P per output channel, operands on the extended basis
+    masks_ext, w_int = orc.conv_operands_ext(w, wl.height, wl.width, wl.batch, level, 2.0 ** 28, delta_pt / 2.0 ** 28)
+    masks = np.ascontiguousarray(masks_ext[:, :level + 1])
+    ext_moduli = [p.moduli[t] for t in orc.ext_moduli_idx(level)]
     dkeys = [hx.ckks_key_load(ctx, hx.from_host(keys[off]), hx.ckks_galois_element(ctx, off)) if off else None for off in offs]
     d_masks = hx.from_host(masks)
+    d_masks_ext = hx.from_host(masks_ext)
     d_cts = [hx.from_host(c) for c in cts]
-    conv = hx.he_conv_batched(ctx, wl.height, wl.width, wl.batch, level, d_cts, dkeys, d_masks,
-                              hx.from_host(w_residues(w_int, p.moduli, level)), wl.c_out)
+    conv = hx.he_conv_batched(ctx, wl.height, wl.width, wl.batch, level, d_cts, dkeys, d_masks_ext,
+                              hx.from_host(w_residues(w_int, ext_moduli, len(ext_moduli) - 1)), wl.c_out,
+                              alignment=hx.HE_CONV_DEFERRED_MODDOWN)
     scale = 2.0 ** 50
     plan = orc.act_schedule(level - 1, scale)
     d_rlk = hx.ckks_key_load(ctx, hx.from_host(rlk), 0)
@@ -147,3 +153,11 @@ def test_cfg5_resnet20_stage3_block_slice():
     want = orc.he_conv([cts[c] for c in sub_in], level, wl.width, keys, masks, w_sub)
     for i in range(len(sub_out)):
         assert np.array_equal(hx.to_host(got[i]), want[i]), f"slice output {i}"
+    # the same slice in the deferred schedule, limb for limb, and equal to the full run's channels where the
+    # inputs coincide is not expected (other input channels): compare with the oracle only
+    got = hx.he_conv_batched(ctx, wl.height, wl.width, wl.batch, level, [d_cts[c] for c in sub_in], dkeys, d_masks_ext,
+                             hx.from_host(w_residues(w_sub, ext_moduli, len(ext_moduli) - 1)), len(sub_out),
+                             alignment=hx.HE_CONV_DEFERRED_MODDOWN)
+    want = orc.he_conv_deferred([cts[c] for c in sub_in], level, wl.width, keys, masks_ext, w_sub)
+    for i in range(len(sub_out)):
+        assert np.array_equal(hx.to_host(got[i]), want[i]), f"deferred slice output {i}"
