@@ -553,6 +553,32 @@ class Oracle:
             outs[o] = self.rescale(acc, level)
         return outs
 
+    # ---------------------------------------------------------------- accumulator (pipeline)
+    def cleaning_mask(self, sts: int) -> np.ndarray:
+        """The plaintext cleaning mask M of the accumulator: ones on the first `sts` slots, zeros on the rest."""
+        m = np.zeros(self.n, dtype=np.float64)
+        m[:sts] = 1.0
+        return m
+
+    def accumulator_merge(self, cts: Sequence[np.ndarray], level: int, sts: int, M: np.ndarray,
+                          rot_keys: Dict[int, np.ndarray]) -> np.ndarray:
+        """The accumulator of the optimised pipeline ("Optimized Inference Pipeline", the merge equation):
+            C_joined = Rescale( sum_{i<g} Rot(C_i (.) M, -i*sts) ),
+        g = len(cts) down-sampled intermediate ciphertexts whose data sit in slots [0, sts); M is the
+        cleaning mask in NTT form [level+1][N]; rot_keys maps the offset -i*sts to its key.  The mask
+        multiplication is followed by the rescale every plaintext product needs (the paper leaves
+        scale management to the library).  Result at level-1, block i in slots [i*sts, (i+1)*sts)."""
+        g = len(cts)
+        if g * sts > self.n:
+            raise ValueError("g * sts exceeds the slot count")
+        total = None
+        for i, ct in enumerate(cts):
+            t = self.ptct_mac([M], [_u64(ct)], level)
+            if i:
+                t = self.rotate(t, level, -i * sts, rot_keys[-i * sts], True)
+            total = t if total is None else self.add(total, t, level)
+        return self.rescale(total, level)
+
     # ----------------------------------------------------------------------- activation
     def act_schedule(self, level: int, scale: float) -> dict:
         """Levels, scales and integer scalars of the degree-7 activation evaluated on a

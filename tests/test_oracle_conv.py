@@ -244,6 +244,32 @@ def test_he_conv_deferred_centre_only_kernel_equals_direct():
     assert np.array_equal(a, b)
 
 
+def test_accumulator_merge_concatenates_cleaned_blocks():
+    """g = 4 intermediate ciphertexts with data in the first quarter of the slots and junk behind it:
+    the merged ciphertext decrypts to the four cleaned blocks side by side; g = 1 is mask-and-rescale."""
+    p = CONFIGS["small_conv"].params()
+    o = Oracle(p)
+    level = p.num_q - 1
+    s, s_ntt = o.gen_secret(10000)
+    g, sts = 4, o.n // 4
+    rng = np.random.default_rng(7)
+    zs = [rng.uniform(-1, 1, o.n) for _ in range(g)]               # slots beyond sts are junk to be cleaned
+    scale = 2.0 ** 40
+    cts = [o.encrypt(z, scale, level, s_ntt, 10001 + i) for i, z in enumerate(zs)]
+    M = o.encode_ntt(o.cleaning_mask(sts), float(p.moduli[level]), level)   # mask at scale q_level: the rescale restores 2^40
+    keys = {-i * sts: o.gen_rotation_key(s, s_ntt, -i * sts, 10100 + i) for i in range(1, g)}
+    out = o.accumulator_merge(cts, level, sts, M, keys)
+    assert out.shape == (2, level, o.N)
+    want = np.concatenate([z[:sts] for z in zs])
+    assert np.abs(o.decrypt(out, level - 1, s_ntt, scale) - want).max() < 1e-5
+    one = o.accumulator_merge(cts[:1], level, sts, M, {})
+    assert np.array_equal(one, o.rescale(o.ptct_mac([M], [cts[0]], level), level))
+    z1 = o.decrypt(one, level - 1, s_ntt, scale)
+    assert np.abs(z1[:sts] - zs[0][:sts]).max() < 1e-5 and np.abs(z1[sts:]).max() < 1e-5
+    with pytest.raises(ValueError):
+        o.accumulator_merge(cts * 2, level, sts, M, keys)
+
+
 def test_activation_polynomial_pins():
     assert activation_reference(np.array([0.0, 1.0, -1.0])).tolist() == [0.0, 1.0, -1.0]
     # p'(x) = 35/16 (1-x^2)^3: flat at +-1
