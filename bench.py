@@ -67,39 +67,48 @@ def parse_args():
     return ap.parse_args()
 
 
-def cpu_baseline(wl, params):
-    """Times the CPU oracle on a bounded sample of the same workload and extrapolates to one step."""
+def cpu_baseline(wl, params, alignment):
+    """Times the CPU oracle on a bounded sample of the same workload and schedule and extrapolates to one step."""
     import numpy as np
     from oracle import Oracle
     from workloads import conv_tap_offsets, uniform_residues
     orc = Oracle(params)
     level = params.num_q - 1
     q = params.moduli
-    rng_ct = uniform_residues((2, level + 1, orc.N), q[:level + 1], "cpu_ct")
+    deferred = alignment == "deferred"
+    ct = uniform_residues((2, level + 1, orc.N), q[:level + 1], "cpu_ct")
     key = uniform_residues((params.dnum, 2, orc.M, orc.N), q, "cpu_key")
-    offs = [o for o in conv_tap_offsets(wl.width) if o]
+    offs = conv_tap_offsets(wl.width)
+    keys = {o: key for o in offs if o}
+    q_mac = [q[t] for t in orc.ext_moduli_idx(level)] if deferred else list(q[:level + 1])
+    pts = [uniform_residues((len(q_mac), orc.N), q_mac, "cpu_pt%d" % i) for i in range(9)]
     t0 = time.perf_counter()
-    digits = orc.modup(rng_ct[1], level)
-    aligned = [orc.rotate(rng_ct, level, o, key, True, digits) for o in offs]
-    t_align = time.perf_counter() - t0                      # one input channel: 1 ModUp + 8 rotations
-    pts = [uniform_residues((level + 1, orc.N), q[:level + 1], "cpu_pt%d" % i) for i in range(9)]
+    if deferred:
+        aligned = orc.align_deferred(ct, level, wl.width, keys)
+    elif alignment == "four_keys":
+        aligned = orc.align_four_keys(ct, level, wl.width, keys)
+    else:
+        aligned = orc.align_direct(ct, level, wl.width, keys)
+    t_align = time.perf_counter() - t0                      # one input channel: its nine aligned copies
     t0 = time.perf_counter()
-    acc = orc.ptct_mac(pts, aligned + [rng_ct], level)
+    acc = orc.mac_ext(pts, aligned, level) if deferred else orc.ptct_mac(pts, aligned, level)
     t_mac = time.perf_counter() - t0                        # 9 taps of one (input, output) channel pair
     t0 = time.perf_counter()
+    if deferred:
+        acc = np.stack([orc.moddown(acc[0], level), orc.moddown(acc[1], level)])
     x = orc.rescale(acc, level)
-    t_resc = time.perf_counter() - t0
+    t_out = time.perf_counter() - t0                        # one output channel: (ModDown and) rescale
     t0 = time.perf_counter()
     orc.poly_activation(x, level - 1, (3 << 40, -(5 << 40), 7 << 40, -(9 << 40)), key)
     t_act = time.perf_counter() - t0
-    step = wl.c_in * t_align + wl.c_in * wl.c_out * t_mac + wl.c_out * (t_resc + t_act)
+    step = wl.c_in * t_align + wl.c_in * wl.c_out * t_mac + wl.c_out * (t_out + t_act)
     cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
     return {
         "value": step * 1e3 / wl.batch, "unit": "ms/image", "cores": cores, "kind": "oracle",
-        "sample": ("oracle timed on one input channel's alignment (1 ModUp + 8 hoisted rotations, %.2f s), one 9-tap "
-                   "multiply-accumulate (%.2f s), one rescale (%.2f s) and one degree-7 activation (%.2f s) at full "
-                   "size, extrapolated to %d alignments, %d 9-tap MACs, %d rescales and activations"
-                   % (t_align, t_mac, t_resc, t_act, wl.c_in, wl.c_in * wl.c_out, wl.c_out)),
+        "sample": ("oracle (%s schedule) timed on one input channel's alignment (%.2f s), one 9-tap multiply-accumulate "
+                   "(%.2f s), one output channel's %srescale (%.2f s) and one degree-7 activation (%.2f s) at full size, "
+                   "extrapolated to %d alignments, %d 9-tap MACs, %d output channels and activations"
+                   % (alignment, t_align, t_mac, "ModDown + " if deferred else "", t_out, t_act, wl.c_in, wl.c_in * wl.c_out, wl.c_out)),
         "step_seconds_extrapolated": step,
     }
 
@@ -224,7 +233,7 @@ def main():
         result["calibration_copy_bytes_each_way"] = 2 * (level + 1) * N * 8
     if args.no_microbench:
         if not args.no_cpu_baseline:
-            result["cpu_baseline"] = cpu_baseline(wl, params)
+            result["cpu_baseline"] = cpu_baseline(wl, params, args.alignment)
         print(json.dumps(result))
         return
     # ---- the two microbenchmark shapes, reported next to the headline value ------------------------
@@ -253,6 +262,22 @@ def main():
         mib = (96 + 12 + 24) if hoisted else (96 + 24 + 24)
         result["rotation_%s_effective_GBs" % name] = rate * mib * 2**20 / 1e9
     del mb_keys, mb_outs
+    # accumulator merge (the optimised pipeline's block-group transition): 4 intermediate ciphertexts with 8192
+    # occupied slots each -> one full ciphertext, at the level the block slice leaves its outputs on
+    acc_level, acc_g, acc_sts = level - 5, 4, 8192
+    acc_in = [t[:, :acc_level + 1].contiguous() for t in ins[:acc_g]]
+    acc_keys = [None] + [hx.ckks_key_load(ctx, base_keys[i].tensor, hx.ckks_galois_element(ctx, -i * acc_sts)) for i in range(1, acc_g)]
+    acc_mask = masks[0, :acc_level + 1].contiguous()
+    acc_out = hx.empty(2, acc_level, N)
+    hx.he_accumulator_merge(ctx, acc_in, acc_level, acc_sts, acc_mask, acc_keys, out=acc_out, ws=ws)
+    torch.cuda.synchronize()
+    reps = 20
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        hx.he_accumulator_merge(ctx, acc_in, acc_level, acc_sts, acc_mask, acc_keys, out=acc_out, ws=ws)
+    torch.cuda.synchronize()
+    result["accumulator_merges_per_s"] = reps / (time.perf_counter() - t0)
+    result["accumulator_merge_shape"] = {"g": acc_g, "sts": acc_sts, "level": acc_level}
     # NTT microbenchmark: 64 polynomials x 30 limbs at N = 2^16, forward then inverse
     p2 = CONFIGS["cfg2_ntt"].params()
     ctx2 = hx.Context(p2)
@@ -272,7 +297,7 @@ def main():
     result["ntt_butterflies_per_s"] = result["ntt_limbs_per_s"] * (N // 2) * p2.log_n
 
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(wl, params)
+        result["cpu_baseline"] = cpu_baseline(wl, params, args.alignment)
     print(json.dumps(result))
 
 

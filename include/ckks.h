@@ -179,6 +179,19 @@ int he_conv_batched(const ckks_ctx* ctx, const he_conv_desc* desc, const uint64_
                     const ckks_key* const* rot_keys, const uint64_t* d_tap_masks, const uint64_t* d_w_res,
                     uint64_t* const* h_d_out, void* d_ws, size_t ws_bytes, void* stream);
 
+/* The accumulator of the optimised pipeline ("Optimized Inference Pipeline", the merge equation): g
+ * down-sampled intermediate ciphertexts whose data occupy slots [0, sts) are cleaned, moved to
+ * disjoint slot ranges and added,
+ *   out = Rescale( sum_{i<g} Rot(C_i (.) M, -i*sts) ),
+ * so that block i lands in slots [i*sts, (i+1)*sts).  d_mask: the encoded cleaning mask M (ones on the
+ * first sts slots), uint64[level+1][N], NTT form; keys[i] the key of offset -i*sts for 1 <= i < g
+ * (keys[0] ignored).  h_d_cts: g <= 16 device pointers uint64[2][level+1][N]; d_out uint64[2][level][N].
+ * Fails with CKKS_ERR_INVALID_ARG if g*sts > N/2.  Workspace from he_accumulator_workspace_bytes(). */
+size_t he_accumulator_workspace_bytes(const ckks_ctx* ctx, uint32_t level, uint32_t g);
+int he_accumulator_merge(const ckks_ctx* ctx, const uint64_t* const* h_d_cts, uint32_t g, uint32_t level, uint32_t sts,
+                         const uint64_t* d_mask, const ckks_key* const* keys, uint64_t* d_out, void* d_ws,
+                         size_t ws_bytes, void* stream);
+
 /* Odd degree-7 polynomial activation on a vector of n_ct channel ciphertexts, four ciphertext
  * products each ("Other Layers": the activation applied independently to every element of the
  * channel vector):  x2 = x*x, x3 = x2*x, x4 = x2*x2 (each rescaled once),

@@ -41,6 +41,7 @@ EXPORTS = (
     "ckks_ntt_fwd", "ckks_ntt_inv", "ckks_key_load", "ckks_key_free", "ckks_galois_element",
     "ckks_keyswitch", "ckks_rotate_hoisted", "ckks_ptct_mac", "ckks_rescale", "ckks_ctct_mul_relin",
     "he_conv_workspace_bytes", "he_conv_batched", "he_poly_act_deg7",
+    "he_accumulator_workspace_bytes", "he_accumulator_merge",
     "ckks_prof_kernel_count", "ckks_prof_kernel_name", "ckks_prof_begin", "ckks_prof_end",
 )
 
@@ -91,6 +92,9 @@ def _bind(path: str):
     lib.he_conv_workspace_bytes.restype = sz
     lib.he_conv_batched.argtypes = [vp, C.POINTER(_ConvDesc), C.POINTER(vp), C.POINTER(vp), vp, vp, C.POINTER(vp), vp, sz, vp]
     lib.he_poly_act_deg7.argtypes = [vp, C.POINTER(vp), u32, u32, C.POINTER(C.c_int64), vp, C.POINTER(vp), vp, sz, vp]
+    lib.he_accumulator_workspace_bytes.argtypes = [vp, u32, u32]
+    lib.he_accumulator_workspace_bytes.restype = sz
+    lib.he_accumulator_merge.argtypes = [vp, C.POINTER(vp), u32, u32, u32, vp, C.POINTER(vp), vp, vp, sz, vp]
     lib.ckks_prof_kernel_count.restype = u32
     lib.ckks_prof_kernel_name.argtypes = [u32]
     lib.ckks_prof_kernel_name.restype = C.c_char_p
@@ -358,6 +362,35 @@ def he_poly_act_deg7(ctx: Context, xs: Sequence[torch.Tensor], level: int, k: Se
     ctx._check(_lib.he_poly_act_deg7(ctx.handle, xa, n, level, ka, rlk.handle if rlk else None, oa, _ptr(ws),
                                      ws.numel() * ws.element_size(), _stream(stream)))
     return outs
+
+
+def he_accumulator_workspace_bytes(ctx: Context, level: int, g: int) -> int:
+    return int(_lib.he_accumulator_workspace_bytes(ctx.handle, level, g))
+
+
+def he_accumulator_merge(ctx: Context, cts: Sequence[torch.Tensor], level: int, sts: int, mask: torch.Tensor,
+                         keys: Sequence[Optional[Key]], out: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None,
+                         stream=None) -> torch.Tensor:
+    """cts: g ciphertexts [2][level+1][N] with data in slots [0, sts); mask [level+1][N]; keys[i] = key of offset
+    -i*sts (keys[0] ignored).  Returns [2][level][N] with block i in slots [i*sts, (i+1)*sts)."""
+    g = len(cts)
+    if g == 0 or len(keys) != g:
+        raise ValueError("need g >= 1 ciphertexts and g key entries (the first may be None)")
+    for t in cts:
+        if t.numel() != 2 * (level + 1) * ctx.N:
+            raise ValueError("each ciphertext must be [2][level+1][N]")
+    if mask.numel() != (level + 1) * ctx.N:
+        raise ValueError("mask must be [level+1][N]")
+    if out is None:
+        out = empty(2, max(level, 1), ctx.N)
+    if out.numel() != 2 * level * ctx.N:
+        raise ValueError("out must be [2][level][N]")
+    ws = _ws(ctx, ws, he_accumulator_workspace_bytes(ctx, level, g))
+    ca = _ptr_array([_ptr(t) for t in cts])
+    ka = _ptr_array([k.handle.value if k is not None else None for k in keys])
+    ctx._check(_lib.he_accumulator_merge(ctx.handle, ca, g, level, sts, _ptr(mask), ka, _ptr(out), _ptr(ws),
+                                         ws.numel() * ws.element_size(), _stream(stream)))
+    return out
 
 
 def ckks_prof_kernel_names() -> List[str]:

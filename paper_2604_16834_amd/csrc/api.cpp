@@ -586,6 +586,66 @@ int he_conv_batched(const ckks_ctx* c, const he_conv_desc* d, const uint64_t* co
     return CKKS_OK;
 }
 
+size_t he_accumulator_workspace_bytes(const ckks_ctx* c, uint32_t level, uint32_t g) {
+    if (!c || !c->dnum || !level_ok(c, level) || level < 1 || g == 0 || g > KS_MAX_BATCH) return 0;
+    const size_t N = c->N, L1 = level + 1;
+    const u32 nb = g - 1 < CT_BATCH ? (g > 1 ? g - 1 : 1) : CT_BATCH;
+    return ws_ks(c, level, nb, nb) + 2 * blk((size_t)g * 2 * L1 * N) + blk(2 * L1 * N) + ws_rescale(c, level, 1);
+}
+
+int he_accumulator_merge(const ckks_ctx* c, const uint64_t* const* h_d_cts, uint32_t g, uint32_t level, uint32_t sts,
+                         const uint64_t* d_mask, const ckks_key* const* keys, uint64_t* d_out, void* d_ws, size_t ws_bytes,
+                         void* stream) {
+    if (!c) return CKKS_ERR_INVALID_ARG;
+    if (!h_d_cts || !d_mask || !d_out || g == 0) return set_err(c, CKKS_ERR_INVALID_ARG, "null pointer or no ciphertexts");
+    if (g > KS_MAX_BATCH) return set_err(c, CKKS_ERR_INVALID_ARG, "at most 16 ciphertexts per merge");
+    if (!c->dnum) return set_err(c, CKKS_ERR_UNSUPPORTED_PARAMS, "context has no key-switching digits");
+    if (!level_ok(c, level) || level < 1) return set_err(c, CKKS_ERR_LEVEL_MISMATCH, "merge needs 1 <= level < num_q");
+    if (sts == 0 || (u64)g * sts > c->N / 2) return set_err(c, CKKS_ERR_INVALID_ARG, "g * sts exceeds the N/2 slots");
+    u32 gal[KS_MAX_BATCH];
+    for (u32 i = 0; i < g; i++) {
+        if (!h_d_cts[i]) return set_err(c, CKKS_ERR_INVALID_ARG, "null ciphertext pointer");
+        gal[i] = ckks_galois_element(c, -(int32_t)(i * sts));
+        if (i == 0) continue;
+        if (!keys || !keys[i]) return set_err(c, CKKS_ERR_NO_KEY, "rotation key missing for a block");
+        if (keys[i]->galois_elt != gal[i]) return set_err(c, CKKS_ERR_NO_KEY, "rotation key does not match the block's offset");
+    }
+    const size_t N = c->N, L1 = level + 1, ct_elems = 2 * L1 * N;
+    const u32 nb = g - 1 < CT_BATCH ? (g > 1 ? g - 1 : 1) : CT_BATCH;
+    Arena ar(d_ws, ws_bytes);
+    KsWs ws;
+    bool ok = carve_ks(c, level, nb, nb, ar, ws);
+    u64* masked = ar.take((size_t)g * ct_elems);   // C_i (.) M
+    u64* rotated = ar.take((size_t)g * ct_elems);  // Rot(C_i (.) M, -i*sts), i >= 1
+    u64* total = ar.take(ct_elems);
+    if (!ok || !ar.ok() || ar.used + ws_rescale(c, level, 1) > ar.cap)
+        return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for the merge");
+    hipStream_t st = (hipStream_t)stream;
+    for (u32 i = 0; i < g; i++)
+        HIP_TRY(launch_mask_mul(c, level, (const u64*)d_mask, (const u64*)h_d_cts[i], masked + i * ct_elems, st));
+    // blocks 1..g-1: every block has its own key; a batch shares the decomposition and ModDown launches
+    for (u32 i0 = 1; i0 < g; i0 += nb) {
+        const u32 n = g - i0 < nb ? g - i0 : nb;
+        const u64* c1s[CT_BATCH];
+        FinalItem items[CT_BATCH];
+        for (u32 b = 0; b < n; b++) c1s[b] = masked + (i0 + b) * ct_elems + L1 * N;
+        int rc = run_modup(c, level, c1s, n, ws, st);
+        if (rc) return rc;
+        for (u32 b = 0; b < n; b++) {
+            HIP_TRY(launch_key_inner(c, level, ws.digits + b * ws.dig_b, keys[i0 + b]->d_key, gal[i0 + b], ws.v + b * ws.v_b, st));
+            items[b] = FinalItem{masked + (i0 + b) * ct_elems, nullptr, nullptr, rotated + (i0 + b) * ct_elems, gal[i0 + b], 0};
+        }
+        if ((rc = run_moddown(c, level, ws, n, items, st))) return rc;
+    }
+    const u64* terms[KS_MAX_BATCH];
+    terms[0] = masked;
+    for (u32 i = 1; i < g; i++) terms[i] = rotated + i * ct_elems;
+    HIP_TRY(launch_ct_sum(c, level, ptr_list(terms, g), g, total, st));
+    const u64* in = total;
+    u64* out = (u64*)d_out;
+    return run_rescale(c, level, &in, L1 * N, &out, 1, ar.rest(), st);
+}
+
 int he_poly_act_deg7(const ckks_ctx* c, const uint64_t* const* h_d_x, uint32_t n_ct, uint32_t level, const int64_t* h_k,
                      const ckks_key* rlk, uint64_t* const* h_d_out, void* d_ws, size_t ws_bytes, void* stream) {
     if (!c) return CKKS_ERR_INVALID_ARG;

@@ -254,6 +254,26 @@ hipError_t launch_weighted_sum(const ckks_ctx* c, u32 level, bool extended, cons
     return hipGetLastError();
 }
 
+// ---- out = sum of n <= KS_MAX_BATCH ciphertexts [2][level+1][N] (the accumulator's additions) ----------
+__global__ __launch_bounds__(PW_THREADS) void ct_sum_kernel(PtrList8 items, u32 n, u64* __restrict__ out,
+                                                            const ModConst* __restrict__ mc, u32 N, u32 level) {
+    const u32 x = blockIdx.x * PW_THREADS + threadIdx.x;
+    if (x >= N) return;
+    const u32 i = blockIdx.y, comp = blockIdx.z;
+    const u64 q = mc[i].q;
+    const size_t o = ((size_t)comp * (level + 1) + i) * N + x;
+    u64 s = items.p[0][o];
+    for (u32 b = 1; b < n; b++) s = add_mod(s, items.p[b][o], q);
+    out[o] = s;
+}
+
+hipError_t launch_ct_sum(const ckks_ctx* c, u32 level, const PtrList8& items, u32 n, u64* out, hipStream_t st) {
+    dim3 grid((c->N + PW_THREADS - 1) / PW_THREADS, level + 1, 2);
+    ProfScope ps__(c, K_LINCOMB2, st, 16.0 * c->N * (level + 1.0) * (n + 1.0), 0.0);
+    hipLaunchKernelGGL(ct_sum_kernel, grid, dim3(PW_THREADS), 0, st, items, n, out, c->d_mc, c->N, level);
+    return hipGetLastError();
+}
+
 // ---- out_b = ka * a_b + kb * b_b (+ add_b) on limbs 0..level, integer scalars given by residues ----
 struct Scalars {
     u64 ka[CKKS_MAX_MODULI];

@@ -161,3 +161,25 @@ def test_cfg5_resnet20_stage3_block_slice():
     want = orc.he_conv_deferred([cts[c] for c in sub_in], level, wl.width, keys, masks_ext, w_sub)
     for i in range(len(sub_out)):
         assert np.array_equal(hx.to_host(got[i]), want[i]), f"deferred slice output {i}"
+
+
+def test_accumulator_merge_at_the_block_group_transition():
+    """Four down-sampled intermediate ciphertexts (8192 occupied slots each, junk behind them) merged into
+    one full ciphertext at N = 2^16, at the level the block slice leaves its outputs on (18): residues
+    against the oracle, slots against the concatenated blocks."""
+    wl = CONFIGS["cfg5_resnet20_stage3"]
+    p = wl.params()
+    orc, ctx = Oracle(p), hx.Context(p)
+    level, g, sts = p.num_q - 6, 4, 8192
+    s, s_ntt = orc.gen_secret(6000)
+    rng = np.random.default_rng(6001)
+    zs = [rng.uniform(-1, 1, orc.n) for _ in range(g)]
+    scale = 2.0 ** 40
+    cts = [orc.encrypt(z, scale, level, s_ntt, 6010 + i) for i, z in enumerate(zs)]
+    M = orc.encode_ntt(orc.cleaning_mask(sts), float(p.moduli[level]), level)
+    keys = {-i * sts: orc.gen_rotation_key(s, s_ntt, -i * sts, 6100 + i) for i in range(1, g)}
+    dkeys = [None] + [hx.ckks_key_load(ctx, hx.from_host(keys[-i * sts]), hx.ckks_galois_element(ctx, -i * sts)) for i in range(1, g)]
+    out = hx.to_host(hx.he_accumulator_merge(ctx, [hx.from_host(c) for c in cts], level, sts, hx.from_host(M), dkeys))
+    assert np.array_equal(out, orc.accumulator_merge(cts, level, sts, M, keys))
+    want = np.concatenate([z[:sts] for z in zs])
+    assert np.abs(orc.decrypt(out, level - 1, s_ntt, scale) - want).max() < 1e-5

@@ -246,6 +246,43 @@ def test_he_conv_equals_composition_of_exported_ops():
         assert np.array_equal(hx.to_host(hx.ckks_rescale(ctx, acc, level)), outs[o])
 
 
+# ----------------------------------------------------------------------------------- accumulator
+@pytest.mark.parametrize("g,level", [(4, 4), (2, 2), (1, 3), (10, 4)])
+def test_accumulator_merge_matches_oracle(g, level):
+    """Cleaned blocks side by side: residues against the oracle, slots against the concatenation.
+    g = 10 takes two batches of rotations; g = 1 is mask-and-rescale."""
+    p = CONFIGS["small_conv"].params()
+    orc, ctx = both(p)
+    s, s_ntt = orc.gen_secret(401)
+    sts = orc.n // 16 if g > 4 else orc.n // 4
+    rng = np.random.default_rng(402 + g)
+    zs = [rng.uniform(-1, 1, orc.n) for _ in range(g)]
+    scale = 2.0 ** 40
+    cts = [orc.encrypt(z, scale, level, s_ntt, 410 + i) for i, z in enumerate(zs)]
+    M = orc.encode_ntt(orc.cleaning_mask(sts), float(p.moduli[level]), level)
+    keys = {-i * sts: orc.gen_rotation_key(s, s_ntt, -i * sts, 430 + i) for i in range(1, g)}
+    dkeys = [None] + [hx.ckks_key_load(ctx, hx.from_host(keys[-i * sts]), hx.ckks_galois_element(ctx, -i * sts)) for i in range(1, g)]
+    out = hx.to_host(hx.he_accumulator_merge(ctx, [hx.from_host(c) for c in cts], level, sts, hx.from_host(M), dkeys))
+    assert np.array_equal(out, orc.accumulator_merge(cts, level, sts, M, keys))
+    want = np.zeros(orc.n)
+    want[:g * sts] = np.concatenate([z[:sts] for z in zs])
+    assert np.abs(orc.decrypt(out, level - 1, s_ntt, scale) - want).max() < 1e-5
+
+
+def test_accumulator_merge_rejects_overfull_and_wrong_keys():
+    p = CONFIGS["small_conv"].params()
+    orc, ctx = both(p)
+    level = 2
+    ct = hx.from_host(rand_ct(np.random.default_rng(3), p.moduli, level, orc.N))
+    mask = hx.empty(level + 1, orc.N)
+    with pytest.raises(hx.CkksError) as e:                 # 3 blocks of n/2 slots do not fit
+        hx.he_accumulator_merge(ctx, [ct] * 3, level, orc.n // 2, mask, [None] * 3)
+    assert e.value.code == hx.binding.CKKS_ERR_INVALID_ARG
+    with pytest.raises(hx.CkksError) as e:
+        hx.he_accumulator_merge(ctx, [ct] * 2, level, orc.n // 2, mask, [None, None])
+    assert e.value.code == hx.binding.CKKS_ERR_NO_KEY
+
+
 # ------------------------------------------------------------------------------------ activation
 @pytest.mark.parametrize("n_ct", [1, 3, 10])
 def test_poly_activation_matches_oracle(n_ct):
