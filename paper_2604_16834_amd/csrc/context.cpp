@@ -62,6 +62,9 @@ extern "C" void ckks_ctx_destroy(ckks_ctx* c) {
     (void)hipFree(c->d_mc);
     (void)hipFree(c->d_tw);
     (void)hipFree(c->d_itw);
+    (void)hipFree(c->d_twf);
+    (void)hipFree(c->d_itwf);
+    (void)hipFree(c->d_mcf);
     (void)hipFree(c->d_modup);
     (void)hipFree(c->d_moddown);
     (void)hipFree(c->d_rescale);
@@ -104,6 +107,7 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
     c->log_hi = p->log_n - c->log_lo;
     c->lazy_terms = 1u << (lazy_log > 12 ? 12 : lazy_log);
     c->small_q = bmax <= 50;
+    c->ntt_f64 = c->small_q && p->log_n >= CKKS_TILE_LOG;
     auto pad = [](u32 v) { return v <= 4 ? 4u : (v <= 8 ? 8u : 16u); };
     c->alpha_pad = pad(alpha);
     c->k_pad = pad(p->num_p);
@@ -111,7 +115,12 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
     c->psi.assign(p->psi, p->psi + M);
 
     c->mc.resize(M);
-    std::vector<TwPair> tw((size_t)M * N), itw((size_t)M * N);
+    // one pair of twiddle tables: integers with Shoup companions, or doubles with twiddle / q
+    std::vector<TwPair> tw, itw;
+    std::vector<TwF> twf, itwf;
+    std::vector<ModConstF> mcf;
+    if (c->ntt_f64) { twf.resize((size_t)M * N); itwf.resize((size_t)M * N); mcf.resize(M); }
+    else { tw.resize((size_t)M * N); itw.resize((size_t)M * N); }
     for (u32 t = 0; t < M; t++) {
         const u64 q = c->mod[t];
         ModConst& m = c->mc[t];
@@ -121,6 +130,12 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
         m.pad = 0;
         m.n_inv = h_invmod(N % q, q);
         m.n_inv_sh = h_shoup(m.n_inv, q);
+        if (c->ntt_f64) {  // every value below is an integer below 2^50: exact as a double; the quotients are correctly rounded
+            mcf[t].q = (double)q;
+            mcf[t].qinv = 1.0 / (double)q;
+            mcf[t].ninv = (double)m.n_inv;
+            mcf[t].ninv_q = (double)m.n_inv / (double)q;
+        }
         std::vector<u64> pw(N);
         pw[0] = 1;
         for (u32 i = 1; i < N; i++) pw[i] = h_mulmod(pw[i - 1], c->psi[t], q);
@@ -131,8 +146,13 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
         for (u32 i = 0; i < N; i++) {
             const u32 r = h_bitrev(i, p->log_n);
             const size_t o = (size_t)t * N + i;
-            tw[o].w = pw[r]; tw[o].s = h_shoup(pw[r], q);
-            itw[o].w = ipw[r]; itw[o].s = h_shoup(ipw[r], q);
+            if (c->ntt_f64) {
+                twf[o].w = (double)pw[r]; twf[o].wq = (double)pw[r] / (double)q;
+                itwf[o].w = (double)ipw[r]; itwf[o].wq = (double)ipw[r] / (double)q;
+            } else {
+                tw[o].w = pw[r]; tw[o].s = h_shoup(pw[r], q);
+                itw[o].w = ipw[r]; itw[o].s = h_shoup(ipw[r], q);
+            }
         }
     }
 
@@ -209,6 +229,9 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
     if (e == hipSuccess) e = upload(c->mc, &c->d_mc);
     if (e == hipSuccess) e = upload(tw, &c->d_tw);
     if (e == hipSuccess) e = upload(itw, &c->d_itw);
+    if (e == hipSuccess) e = upload(twf, &c->d_twf);
+    if (e == hipSuccess) e = upload(itwf, &c->d_itwf);
+    if (e == hipSuccess) e = upload(mcf, &c->d_mcf);
     if (e == hipSuccess) e = upload(modup, &c->d_modup);
     if (e == hipSuccess) e = upload(moddown, &c->d_moddown);
     if (e == hipSuccess) e = upload(resc, &c->d_rescale);

@@ -26,6 +26,16 @@ struct __attribute__((aligned(16))) TwPair {
     u64 w, s;
 };
 
+// the same for the double-precision butterflies: the twiddle as a double and twiddle / q rounded to nearest
+struct __attribute__((aligned(16))) TwF {
+    double w, wq;
+};
+// per-modulus constants of the double-precision butterflies
+struct ModConstF {
+    double q, qinv;        // the modulus and 1/q rounded to nearest
+    double ninv, ninv_q;   // N^-1 mod q and (N^-1 mod q) / q
+};
+
 // kernel classes, for the optional per-kernel timing (ckks_prof_begin / ckks_prof_end)
 enum KernelId {
     K_NTT_FWD_HI = 0, K_NTT_FWD_LO, K_NTT_INV_LO, K_NTT_INV_HI, K_MODUP_CONV, K_KEY_INNER, K_MODDOWN_CONV, K_MODDOWN_FINAL,
@@ -79,8 +89,12 @@ struct ckks_ctx {
 
     // device tables
     ModConst* d_mc = nullptr;         // [M]
-    TwPair* d_tw = nullptr;           // [M][N]  psi^bitrev(i) with its Shoup companion
+    TwPair* d_tw = nullptr;           // [M][N]  psi^bitrev(i) with its Shoup companion   (integer butterflies)
     TwPair* d_itw = nullptr;          // [M][N]  psi^-bitrev(i) with its Shoup companion
+    bool ntt_f64 = false;             // moduli below 2^50 and N >= 2^11: double-precision butterflies, tables below instead
+    TwF* d_twf = nullptr;             // [M][N]  psi^bitrev(i) and psi^bitrev(i) / q as doubles
+    TwF* d_itwf = nullptr;
+    ModConstF* d_mcf = nullptr;       // [M]
     u64* d_modup = nullptr;           // per level, per digit: see modup_digit_stride()
     u64* d_moddown = nullptr;         // phat_inv[k_pad], phat_inv_sh[k_pad], phat_q[num_q][k_pad], pinv[num_q], pinv_sh[num_q], negp[num_q]
     u64* d_rescale = nullptr;         // [num_q][num_q][3]: (q_l^-1 mod q_i, its Shoup companion, q_l mod q_i)

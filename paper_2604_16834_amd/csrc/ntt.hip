@@ -12,65 +12,171 @@
 //             registers with three exchanges through (padded, double-buffered) LDS.
 // The bit-reversed output order falls out of this split with no transpose.  The inverse runs the
 // mirrored lo pass first, then the mirrored hi pass, and folds the 1/N into its last store.
-// Twiddles psi^bitrev(i) sit in one table per modulus, each with its Shoup companion in the same
-// 16-byte word; the index of the twiddle of a butterfly group obeys T(next stage) = 2*T + bit, so a
-// thread needs only the index of its group at the first stage of a round.
-// Butterflies are lazy: forward values are never corrected on the way (they stay below 35q < 2^64),
-// inverse values are kept in [0, 2q); the last pass stores canonical residues.  Rings below 2^11 use a plain one-tile kernel.
+// Twiddles psi^bitrev(i) sit in one table per modulus, 16 bytes per entry; the index of the twiddle of
+// a butterfly group obeys T(next stage) = 2*T + bit, so a thread needs only the index of its group at
+// the first stage of a round.
+//
+// Two butterfly arithmetics, chosen per context (both give the same canonical residues):
+//   ArithU64  any modulus below 2^58: 64-bit Shoup multiplication (twiddle + precomputed quotient), lazy
+//             values (forward: no correction at all, below 35q < 2^64; inverse: kept in [0, 2q)).
+//   ArithF64  every modulus below 2^50: residues are integers held in doubles and the twiddle product is
+//             reduced with fused multiply-adds: for |y| < 2^51, h = y*w rounded, l = fma(y, w, -h) its
+//             exact error, c = the integer nearest to y*(w/q) (one fma against 1.5*2^52), and
+//             fma(-c, q, h) + l = y*w - c*q exactly, of magnitude below 0.63 q: six double-precision
+//             operations where the integer path spends more than twenty 32-bit ones, which moves the
+//             lo pass from instruction issue to the HBM roof.  Values are brought back to |v| <= q/2 + 1
+//             (three operations) after every round of at most three forward stages and after every sum of
+//             an inverse butterfly, so every multiplicand stays below 2q < 2^51 and every sum below 2^53:
+//             all arithmetic is exact.  Between the two passes the data sit in HBM as doubles.
+// Rings below 2^11 use a plain one-tile integer kernel.
 #include "ctx.h"
+
+#pragma clang fp contract(off)  // the error-free transformations below need every product and sum as written
 
 #define NTT_THREADS 256
 #define NTT_TILE 2048
 #define LDS_PAD(p) ((p) + ((p) >> 3))        // keeps all three exchange patterns (almost) conflict-free
 #define LDS_PADDED_WORDS (NTT_TILE + NTT_TILE / 8)
 
+// ---- 64-bit integer arithmetic --------------------------------------------------------------------------
 // Forward butterfly with no correction at all: the Shoup product t is in [0, 2q) for ANY 64-bit y, so
 // both outputs stay non-negative and grow by at most 2q per stage: below (1 + 2*17) q < 2^64 for every
 // supported modulus (q < 2^58) over a whole transform.  One word reduction at the very end.
-__device__ __forceinline__ void fwd_bf(u64& x, u64& y, const TwPair w, u64 q) {
-    const u64 t = mul_shoup_lazy(y, w.w, w.s, q);
-    y = x + 2 * q - t;
-    x = x + t;
-}
+struct ArithU64 {
+    typedef u64 E;
+    typedef TwPair TW;
+    typedef ModConst MC;
+    static __device__ __forceinline__ E load_first(u64 raw, const MC&, bool /*inverse*/) { return raw; }
+    static __device__ __forceinline__ E load_mid(u64 raw) { return raw; }
+    static __device__ __forceinline__ u64 store_mid(E v) { return v; }
+    static __device__ __forceinline__ u64 store_fwd_final(E v, const MC& m) { return reduce_word(v, m); }
+    static __device__ __forceinline__ u64 store_inv_final(E v, const MC& m) { return mul_shoup(v, m.n_inv, m.n_inv_sh, m.q); }
+    static __device__ __forceinline__ void fwd_bf(E& x, E& y, const TW w, const MC& m) {
+        const u64 t = mul_shoup_lazy(y, w.w, w.s, m.q);
+        y = x + 2 * m.q - t;
+        x = x + t;
+    }
+    static __device__ __forceinline__ void inv_bf(E& x, E& y, const TW w, const MC& m) {
+        const u64 two_q = 2 * m.q;
+        u64 s = x + y;
+        if (s >= two_q) s -= two_q;
+        const u64 d = x + two_q - y;
+        x = s;
+        y = mul_shoup_lazy(d, w.w, w.s, m.q);
+    }
+    static __device__ __forceinline__ void fwd_round_end(E*, const MC&) {}
+};
 
-__device__ __forceinline__ void inv_bf(u64& x, u64& y, const TwPair w, u64 q) {
-    const u64 two_q = 2 * q;
-    u64 s = x + y;
-    if (s >= two_q) s -= two_q;
-    const u64 d = x + two_q - y;
-    x = s;
-    y = mul_shoup_lazy(d, w.w, w.s, q);
-}
-
+// ---- double-precision arithmetic for moduli below 2^50 -----------------------------------------------------
+#define F64_MAGIC 6755399441055744.0  // 1.5 * 2^52: adding it rounds to the nearest integer (for magnitudes below 2^51)
+#define F64_2P52 4503599627370496.0
+struct ArithF64 {
+    typedef double E;
+    typedef TwF TW;
+    typedef ModConstF MC;
+    // the integer nearest to v * c (|v * c| < 2^51), from the exact product: one rounding only
+    static __device__ __forceinline__ double round_mul(double v, double c) { return __builtin_fma(v, c, F64_MAGIC) - F64_MAGIC; }
+    // v - q * round(v / q): |result| <= q/2 + 1 for integer |v| < 2^53
+    static __device__ __forceinline__ double reduce(double v, const MC& m) { return __builtin_fma(-round_mul(v, m.qinv), m.q, v); }
+    // y * w - q * round(y * w / q), exact, magnitude below 0.63 q; needs |y| < 2^51, 0 <= w < q, wq = w / q rounded
+    static __device__ __forceinline__ double mulmod(double y, double w, double wq, double q) {
+        const double h = y * w;
+        const double l = __builtin_fma(y, w, -h);
+        const double c = round_mul(y, wq);
+        return __builtin_fma(-c, q, h) + l;
+    }
+    // canonical residues below 2^52 <-> doubles through the mantissa of 2^52 + v
+    static __device__ __forceinline__ double from_u64(u64 raw) { return __longlong_as_double((long long)(raw | 0x4330000000000000ull)) - F64_2P52; }
+    static __device__ __forceinline__ u64 to_u64(double v) { return (u64)__double_as_longlong(v + F64_2P52) & 0x000fffffffffffffull; }
+    static __device__ __forceinline__ u64 canonical(double v, const MC& m) {  // |v| <= q/2 + 1 -> [0, q)
+        return to_u64(v < 0.0 ? v + m.q : v);
+    }
+    static __device__ __forceinline__ E load_first(u64 raw, const MC& m, bool) { return reduce(from_u64(raw), m); }
+    static __device__ __forceinline__ E load_mid(u64 raw) { return __longlong_as_double((long long)raw); }
+    static __device__ __forceinline__ u64 store_mid(E v) { return (u64)__double_as_longlong(v); }
+    static __device__ __forceinline__ u64 store_fwd_final(E v, const MC& m) { return canonical(v, m); }  // after fwd_round_end
+    static __device__ __forceinline__ u64 store_inv_final(E v, const MC& m) { return canonical(mulmod(v, m.ninv, m.ninv_q, m.q), m); }
+    static __device__ __forceinline__ void fwd_bf(E& x, E& y, const TW w, const MC& m) {
+        const double t = mulmod(y, w.w, w.wq, m.q);
+        y = x - t;
+        x = x + t;
+    }
+    static __device__ __forceinline__ void inv_bf(E& x, E& y, const TW w, const MC& m) {
+        const double s = x + y, d = x - y;
+        x = reduce(s, m);
+        y = mulmod(d, w.w, w.wq, m.q);
+    }
+    static __device__ __forceinline__ void fwd_round_end(E* v, const MC& m) {
+#pragma unroll
+        for (int j = 0; j < 8; j++) v[j] = reduce(v[j], m);
+    }
+};
 
 // S radix-2 stages on 2^S "rows" of KC independent columns held in registers, v[row*KC + col];
 // row bit S-1 is the largest distance.  T = twiddle index of this group at the first stage.
-template <int S, int KC>
-__device__ __forceinline__ void fwd_rows(u64* v, const TwPair* __restrict__ tw, u32 T, u64 q) {
+template <class A, int S, int KC>
+__device__ __forceinline__ void fwd_rows(typename A::E* v, const typename A::TW* __restrict__ tw, u32 T, const typename A::MC& m) {
 #pragma unroll
     for (int a = 0; a < S; a++) {
         const int half = (1 << S) >> (a + 1);
 #pragma unroll
         for (int rr = 0; rr < (1 << S); rr++) {
             if (rr & half) continue;
-            const TwPair w = tw[(T << a) + (rr >> (S - a))];
+            const typename A::TW w = tw[(T << a) + (rr >> (S - a))];
 #pragma unroll
-            for (int kc = 0; kc < KC; kc++) fwd_bf(v[rr * KC + kc], v[(rr + half) * KC + kc], w, q);
+            for (int kc = 0; kc < KC; kc++) A::fwd_bf(v[rr * KC + kc], v[(rr + half) * KC + kc], w, m);
         }
     }
 }
 
-template <int S, int KC>
-__device__ __forceinline__ void inv_rows(u64* v, const TwPair* __restrict__ tw, u32 T, u64 q) {
+template <class A, int S, int KC>
+__device__ __forceinline__ void inv_rows(typename A::E* v, const typename A::TW* __restrict__ tw, u32 T, const typename A::MC& m) {
 #pragma unroll
     for (int a = S - 1; a >= 0; a--) {
         const int half = (1 << S) >> (a + 1);
 #pragma unroll
         for (int rr = 0; rr < (1 << S); rr++) {
             if (rr & half) continue;
-            const TwPair w = tw[(T << a) + (rr >> (S - a))];
+            const typename A::TW w = tw[(T << a) + (rr >> (S - a))];
 #pragma unroll
-            for (int kc = 0; kc < KC; kc++) inv_bf(v[rr * KC + kc], v[(rr + half) * KC + kc], w, q);
+            for (int kc = 0; kc < KC; kc++) A::inv_bf(v[rr * KC + kc], v[(rr + half) * KC + kc], w, m);
+        }
+    }
+}
+
+// The same with the round's 2^S - 1 twiddles already in registers (tv[(1 << a) - 1 + j] = tw[(T << a) + j]):
+// the lo pass requests the twiddles of the next round before it starts the current one, so their
+// latency (they come from L2) hides behind a round of butterflies and an LDS exchange.
+template <class A, int S>
+__device__ __forceinline__ void load_tw(const typename A::TW* __restrict__ tw, u32 T, typename A::TW* tv) {
+#pragma unroll
+    for (int a = 0; a < S; a++)
+#pragma unroll
+        for (int j = 0; j < (1 << a); j++) tv[(1 << a) - 1 + j] = tw[(T << a) + j];
+}
+
+template <class A, int S>
+__device__ __forceinline__ void fwd_rows_pre(typename A::E* v, const typename A::TW* tv, const typename A::MC& m) {
+#pragma unroll
+    for (int a = 0; a < S; a++) {
+        const int half = (1 << S) >> (a + 1);
+#pragma unroll
+        for (int rr = 0; rr < (1 << S); rr++) {
+            if (rr & half) continue;
+            A::fwd_bf(v[rr], v[rr + half], tv[(1 << a) - 1 + (rr >> (S - a))], m);
+        }
+    }
+}
+
+template <class A, int S>
+__device__ __forceinline__ void inv_rows_pre(typename A::E* v, const typename A::TW* tv, const typename A::MC& m) {
+#pragma unroll
+    for (int a = S - 1; a >= 0; a--) {
+        const int half = (1 << S) >> (a + 1);
+#pragma unroll
+        for (int rr = 0; rr < (1 << S); rr++) {
+            if (rr & half) continue;
+            A::inv_bf(v[rr], v[rr + half], tv[(1 << a) - 1 + (rr >> (S - a))], m);
         }
     }
 }
@@ -80,9 +186,10 @@ struct NttArgs {
     u64* dst;
     size_t src_bstride;  // in limb-polys
     size_t dst_bstride;
-    const ModConst* mc;
-    const TwPair* tw;    // [M][N]
+    const void* mc;      // [M] ModConst or ModConstF
+    const void* tw;      // [M][N] TwPair or TwF
     u32 log_n, log_lo, log_hi;
+    u32 first;           // this pass reads the caller's canonical residues (else the other pass's intermediate form)
     u32 last;            // this pass writes the final result (canonical; inverse: times 1/N)
     u32 batch;           // batch items (each pl.n limb-polys)
     u32 lo_group;        // slices per group of the lo-pass numbering (0: plain)
@@ -108,20 +215,22 @@ __device__ __forceinline__ LoTile lo_tile(u32 log_hi, u32 grp) {
     return r;
 }
 
+template <class A>
 struct PolyRef {
     const u64* src;
     u64* dst;
-    const TwPair* tw;
-    ModConst mc;
+    const typename A::TW* tw;
+    typename A::MC mc;
 };
 
-__device__ __forceinline__ PolyRef poly_ref(const NttArgs& A, const PolyList& pl, u32 b, u32 a) {
+template <class A>
+__device__ __forceinline__ PolyRef<A> poly_ref(const NttArgs& args, const PolyList& pl, u32 b, u32 a) {
     const u32 m_idx = pl.mod[a];
-    PolyRef r;
-    r.src = (A.use_src_list ? A.src_list.p[b] : A.src + (((size_t)b * A.src_bstride) << A.log_n)) + ((size_t)pl.spos[a] << A.log_n);
-    r.dst = A.dst + (((size_t)b * A.dst_bstride + pl.dpos[a]) << A.log_n);
-    r.tw = A.tw + ((size_t)m_idx << A.log_n);
-    r.mc = A.mc[m_idx];
+    PolyRef<A> r;
+    r.src = (args.use_src_list ? args.src_list.p[b] : args.src + (((size_t)b * args.src_bstride) << args.log_n)) + ((size_t)pl.spos[a] << args.log_n);
+    r.dst = args.dst + (((size_t)b * args.dst_bstride + pl.dpos[a]) << args.log_n);
+    r.tw = (const typename A::TW*)args.tw + ((size_t)m_idx << args.log_n);
+    r.mc = ((const typename A::MC*)args.mc)[m_idx];
     return r;
 }
 
@@ -131,92 +240,117 @@ __device__ __forceinline__ PolyRef poly_ref(const NttArgs& A, const PolyList& pl
 //   round B: thread = (d3, pos % 32),      points over d2          (distances 128, 64, 32)
 //   round C: thread = (d3, d2, d0),        points over d1          (distances 16, 8, 4)
 //   round D: thread = pos / 8,             8 consecutive points    (distances 2, 1)
-__global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_kernel(NttArgs A, PolyList pl) {
-    __shared__ u64 buf0[LDS_PADDED_WORDS];
-    __shared__ u64 buf1[LDS_PADDED_WORDS];
+template <class A>
+__global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_kernel(NttArgs args, PolyList pl) {
+    typedef typename A::E E;
+    __shared__ E buf0[LDS_PADDED_WORDS];
+    __shared__ E buf1[LDS_PADDED_WORDS];
     const u32 tid = threadIdx.x;
-    const LoTile tile = lo_tile(A.log_hi, A.lo_group);
+    const LoTile tile = lo_tile(args.log_hi, args.lo_group);
     const u32 blk = tile.blk;
-    const PolyRef P = poly_ref(A, pl, tile.b, tile.a);
-    const u64 q = P.mc.q;
+    const PolyRef<A> P = poly_ref<A>(args, pl, tile.b, tile.a);
     const u64* src = P.src + ((size_t)blk << 11);
     u64* dst = P.dst + ((size_t)blk << 11);
-    const u32 TA = (1u << A.log_hi) + blk;
+    const u32 TA = (1u << args.log_hi) + blk;
     const u32 d3 = tid >> 5, x5 = tid & 31, d2 = (tid >> 2) & 7, d0 = tid & 3;
-    u64 v[8];
+    typedef typename A::TW TW;
+    E v[8];
+    TW wa[7], wb[7], wc[7], wd[6];
+    load_tw<A, 3>(P.tw, TA, wa);
+    load_tw<A, 3>(P.tw, 8 * TA + d3, wb);
+    if (args.first) {
 #pragma unroll
-    for (int j = 0; j < 8; j++) v[j] = src[tid + 256 * j];
-    fwd_rows<3, 1>(v, P.tw, TA, q);
+        for (int j = 0; j < 8; j++) v[j] = A::load_first(src[tid + 256 * j], P.mc, false);
+    } else {
+#pragma unroll
+        for (int j = 0; j < 8; j++) v[j] = A::load_mid(src[tid + 256 * j]);
+    }
+    fwd_rows_pre<A, 3>(v, wa, P.mc);
+    A::fwd_round_end(v, P.mc);
+    load_tw<A, 3>(P.tw, 64 * TA + 8 * d3 + d2, wc);
 #pragma unroll
     for (int j = 0; j < 8; j++) buf0[LDS_PAD(tid + 256 * j)] = v[j];
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < 8; j++) v[j] = buf0[LDS_PAD(d3 * 256 + 32 * j + x5)];
-    fwd_rows<3, 1>(v, P.tw, 8 * TA + d3, q);
+    fwd_rows_pre<A, 3>(v, wb, P.mc);
+    A::fwd_round_end(v, P.mc);
+    load_tw<A, 2>(P.tw, 512 * TA + 2 * tid, wd);
+    load_tw<A, 2>(P.tw, 512 * TA + 2 * tid + 1, wd + 3);
 #pragma unroll
     for (int j = 0; j < 8; j++) buf1[LDS_PAD(d3 * 256 + 32 * j + x5)] = v[j];
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < 8; j++) v[j] = buf1[LDS_PAD(d3 * 256 + d2 * 32 + 4 * j + d0)];
-    fwd_rows<3, 1>(v, P.tw, 64 * TA + 8 * d3 + d2, q);
+    fwd_rows_pre<A, 3>(v, wc, P.mc);
+    A::fwd_round_end(v, P.mc);
 #pragma unroll
     for (int j = 0; j < 8; j++) buf0[LDS_PAD(d3 * 256 + d2 * 32 + 4 * j + d0)] = v[j];
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < 8; j++) v[j] = buf0[LDS_PAD(8 * tid + j)];
-    fwd_rows<2, 1>(v, P.tw, 512 * TA + 2 * tid, q);
-    fwd_rows<2, 1>(v + 4, P.tw, 512 * TA + 2 * tid + 1, q);
+    fwd_rows_pre<A, 2>(v, wd, P.mc);
+    fwd_rows_pre<A, 2>(v + 4, wd + 3, P.mc);
+    A::fwd_round_end(v, P.mc);
     ulonglong2* out = reinterpret_cast<ulonglong2*>(dst + 8 * tid);
 #pragma unroll
-    for (int j = 0; j < 4; j++) out[j] = make_ulonglong2(reduce_word(v[2 * j], P.mc), reduce_word(v[2 * j + 1], P.mc));
+    for (int j = 0; j < 4; j++) out[j] = make_ulonglong2(A::store_fwd_final(v[2 * j], P.mc), A::store_fwd_final(v[2 * j + 1], P.mc));
 }
 
-__global__ __launch_bounds__(NTT_THREADS) void ntt_inv_lo_kernel(NttArgs A, PolyList pl) {
-    __shared__ u64 buf0[LDS_PADDED_WORDS];
-    __shared__ u64 buf1[LDS_PADDED_WORDS];
+template <class A>
+__global__ __launch_bounds__(NTT_THREADS) void ntt_inv_lo_kernel(NttArgs args, PolyList pl) {
+    typedef typename A::E E;
+    __shared__ E buf0[LDS_PADDED_WORDS];
+    __shared__ E buf1[LDS_PADDED_WORDS];
     const u32 tid = threadIdx.x;
-    const LoTile tile = lo_tile(A.log_hi, A.lo_group);
+    const LoTile tile = lo_tile(args.log_hi, args.lo_group);
     const u32 blk = tile.blk;
-    const PolyRef P = poly_ref(A, pl, tile.b, tile.a);
-    const u64 q = P.mc.q;
+    const PolyRef<A> P = poly_ref<A>(args, pl, tile.b, tile.a);
     const u64* src = P.src + ((size_t)blk << 11);
     u64* dst = P.dst + ((size_t)blk << 11);
-    const u32 TA = (1u << A.log_hi) + blk;
+    const u32 TA = (1u << args.log_hi) + blk;
     const u32 d3 = tid >> 5, x5 = tid & 31, d2 = (tid >> 2) & 7, d0 = tid & 3;
-    u64 v[8];
+    typedef typename A::TW TW;
+    E v[8];
+    TW wa[7], wb[7], wc[7], wd[6];
+    load_tw<A, 2>(P.tw, 512 * TA + 2 * tid, wd);
+    load_tw<A, 2>(P.tw, 512 * TA + 2 * tid + 1, wd + 3);
+    load_tw<A, 3>(P.tw, 64 * TA + 8 * d3 + d2, wc);
     const ulonglong2* in = reinterpret_cast<const ulonglong2*>(src + 8 * tid);
 #pragma unroll
     for (int j = 0; j < 4; j++) {
         const ulonglong2 t = in[j];
-        v[2 * j] = t.x;
-        v[2 * j + 1] = t.y;
+        v[2 * j] = A::load_first(t.x, P.mc, true);
+        v[2 * j + 1] = A::load_first(t.y, P.mc, true);
     }
-    inv_rows<2, 1>(v, P.tw, 512 * TA + 2 * tid, q);
-    inv_rows<2, 1>(v + 4, P.tw, 512 * TA + 2 * tid + 1, q);
+    inv_rows_pre<A, 2>(v, wd, P.mc);
+    inv_rows_pre<A, 2>(v + 4, wd + 3, P.mc);
+    load_tw<A, 3>(P.tw, 8 * TA + d3, wb);
 #pragma unroll
     for (int j = 0; j < 8; j++) buf0[LDS_PAD(8 * tid + j)] = v[j];
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < 8; j++) v[j] = buf0[LDS_PAD(d3 * 256 + d2 * 32 + 4 * j + d0)];
-    inv_rows<3, 1>(v, P.tw, 64 * TA + 8 * d3 + d2, q);
+    inv_rows_pre<A, 3>(v, wc, P.mc);
+    load_tw<A, 3>(P.tw, TA, wa);
 #pragma unroll
     for (int j = 0; j < 8; j++) buf1[LDS_PAD(d3 * 256 + d2 * 32 + 4 * j + d0)] = v[j];
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < 8; j++) v[j] = buf1[LDS_PAD(d3 * 256 + 32 * j + x5)];
-    inv_rows<3, 1>(v, P.tw, 8 * TA + d3, q);
+    inv_rows_pre<A, 3>(v, wb, P.mc);
 #pragma unroll
     for (int j = 0; j < 8; j++) buf0[LDS_PAD(d3 * 256 + 32 * j + x5)] = v[j];
     __syncthreads();
 #pragma unroll
     for (int j = 0; j < 8; j++) v[j] = buf0[LDS_PAD(tid + 256 * j)];
-    inv_rows<3, 1>(v, P.tw, TA, q);
-    if (A.last) {
+    inv_rows_pre<A, 3>(v, wa, P.mc);
+    if (args.last) {
 #pragma unroll
-        for (int j = 0; j < 8; j++) dst[tid + 256 * j] = mul_shoup(v[j], P.mc.n_inv, P.mc.n_inv_sh, q);
+        for (int j = 0; j < 8; j++) dst[tid + 256 * j] = A::store_inv_final(v[j], P.mc);
     } else {
 #pragma unroll
-        for (int j = 0; j < 8; j++) dst[tid + 256 * j] = v[j];  // lazy [0,2q): the hi pass follows
+        for (int j = 0; j < 8; j++) dst[tid + 256 * j] = A::store_mid(v[j]);  // the hi pass follows
     }
 }
 
@@ -225,33 +359,37 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_inv_lo_kernel(NttArgs A, Poly
 // LOG_HI <= 3: a thread holds all R rows of 8/R columns (no exchange).
 // LOG_HI >= 4: round 1 = radix 8 over rows r0 + (R/8)*j of one column; exchange through LDS;
 //              round 2 = the remaining LOG_HI-3 stages over R/8 consecutive rows of 64/R adjacent columns.
-template <int LOG_HI>
-__global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_hi_kernel(NttArgs A, PolyList pl) {
+// The forward hi pass is the first pass of a transform (reads canonical residues, writes the
+// intermediate form); the inverse hi pass is the last one.
+template <class A, int LOG_HI>
+__global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_hi_kernel(NttArgs args, PolyList pl) {
+    typedef typename A::E E;
     constexpr int R = 1 << LOG_HI, CC = NTT_TILE / R;
     const u32 tid = threadIdx.x;
-    const PolyRef P = poly_ref(A, pl, blockIdx.y / pl.n, blockIdx.y % pl.n);
-    const u64 q = P.mc.q;
+    const PolyRef<A> P = poly_ref<A>(args, pl, blockIdx.y / pl.n, blockIdx.y % pl.n);
     const u64* src = P.src + (size_t)blockIdx.x * CC;
     u64* dst = P.dst + (size_t)blockIdx.x * CC;
-    u64 v[8];
+    E v[8];
     if constexpr (LOG_HI <= 3) {
         constexpr int KC = 8 / R;
 #pragma unroll
         for (int rr = 0; rr < R; rr++)
 #pragma unroll
-            for (int kc = 0; kc < KC; kc++) v[rr * KC + kc] = src[((size_t)rr << 11) + kc * 256 + tid];
-        fwd_rows<LOG_HI, KC>(v, P.tw, 1, q);
+            for (int kc = 0; kc < KC; kc++) v[rr * KC + kc] = A::load_first(src[((size_t)rr << 11) + kc * 256 + tid], P.mc, false);
+        fwd_rows<A, LOG_HI, KC>(v, P.tw, 1, P.mc);
+        A::fwd_round_end(v, P.mc);
 #pragma unroll
         for (int rr = 0; rr < R; rr++)
 #pragma unroll
-            for (int kc = 0; kc < KC; kc++) dst[((size_t)rr << 11) + kc * 256 + tid] = v[rr * KC + kc];
+            for (int kc = 0; kc < KC; kc++) dst[((size_t)rr << 11) + kc * 256 + tid] = A::store_mid(v[rr * KC + kc]);
     } else {
-        __shared__ __attribute__((aligned(16))) u64 lds[NTT_TILE];
+        __shared__ __attribute__((aligned(16))) E lds[NTT_TILE];
         constexpr int R8 = R / 8, S2 = LOG_HI - 3, KC2 = 8 / R8;
         const u32 r0 = tid / CC, col = tid % CC;
 #pragma unroll
-        for (int j = 0; j < 8; j++) v[j] = src[((size_t)(r0 + R8 * j) << 11) + col];
-        fwd_rows<3, 1>(v, P.tw, 1, q);
+        for (int j = 0; j < 8; j++) v[j] = A::load_first(src[((size_t)(r0 + R8 * j) << 11) + col], P.mc, false);
+        fwd_rows<A, 3, 1>(v, P.tw, 1, P.mc);
+        A::fwd_round_end(v, P.mc);
 #pragma unroll
         for (int j = 0; j < 8; j++) lds[(r0 + R8 * j) * CC + col] = v[j];
         __syncthreads();
@@ -260,43 +398,43 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_hi_kernel(NttArgs A, Poly
         for (int rr = 0; rr < R8; rr++)
 #pragma unroll
             for (int kc = 0; kc < KC2; kc++) v[rr * KC2 + kc] = lds[(G * R8 + rr) * CC + cg * KC2 + kc];
-        fwd_rows<S2, KC2>(v, P.tw, 8 + G, q);
+        fwd_rows<A, S2, KC2>(v, P.tw, 8 + G, P.mc);
+        A::fwd_round_end(v, P.mc);
 #pragma unroll
         for (int rr = 0; rr < R8; rr++)
 #pragma unroll
-            for (int kc = 0; kc < KC2; kc++) dst[((size_t)(G * R8 + rr) << 11) + cg * KC2 + kc] = v[rr * KC2 + kc];
+            for (int kc = 0; kc < KC2; kc++) dst[((size_t)(G * R8 + rr) << 11) + cg * KC2 + kc] = A::store_mid(v[rr * KC2 + kc]);
     }
 }
 
-template <int LOG_HI>
-__global__ __launch_bounds__(NTT_THREADS) void ntt_inv_hi_kernel(NttArgs A, PolyList pl) {
+template <class A, int LOG_HI>
+__global__ __launch_bounds__(NTT_THREADS) void ntt_inv_hi_kernel(NttArgs args, PolyList pl) {
+    typedef typename A::E E;
     constexpr int R = 1 << LOG_HI, CC = NTT_TILE / R;
     const u32 tid = threadIdx.x;
-    const PolyRef P = poly_ref(A, pl, blockIdx.y / pl.n, blockIdx.y % pl.n);
-    const u64 q = P.mc.q;
+    const PolyRef<A> P = poly_ref<A>(args, pl, blockIdx.y / pl.n, blockIdx.y % pl.n);
     u64* dst = P.dst + (size_t)blockIdx.x * CC;  // the lo pass has already moved the data to dst
-    u64 v[8];
+    E v[8];
     if constexpr (LOG_HI <= 3) {
         constexpr int KC = 8 / R;
 #pragma unroll
         for (int rr = 0; rr < R; rr++)
 #pragma unroll
-            for (int kc = 0; kc < KC; kc++) v[rr * KC + kc] = dst[((size_t)rr << 11) + kc * 256 + tid];
-        inv_rows<LOG_HI, KC>(v, P.tw, 1, q);
+            for (int kc = 0; kc < KC; kc++) v[rr * KC + kc] = A::load_mid(dst[((size_t)rr << 11) + kc * 256 + tid]);
+        inv_rows<A, LOG_HI, KC>(v, P.tw, 1, P.mc);
 #pragma unroll
         for (int rr = 0; rr < R; rr++)
 #pragma unroll
-            for (int kc = 0; kc < KC; kc++)
-                dst[((size_t)rr << 11) + kc * 256 + tid] = mul_shoup(v[rr * KC + kc], P.mc.n_inv, P.mc.n_inv_sh, q);
+            for (int kc = 0; kc < KC; kc++) dst[((size_t)rr << 11) + kc * 256 + tid] = A::store_inv_final(v[rr * KC + kc], P.mc);
     } else {
-        __shared__ __attribute__((aligned(16))) u64 lds[NTT_TILE];
+        __shared__ __attribute__((aligned(16))) E lds[NTT_TILE];
         constexpr int R8 = R / 8, S2 = LOG_HI - 3, KC2 = 8 / R8;
         const u32 G = tid >> 5, cg = tid & 31;
 #pragma unroll
         for (int rr = 0; rr < R8; rr++)
 #pragma unroll
-            for (int kc = 0; kc < KC2; kc++) v[rr * KC2 + kc] = dst[((size_t)(G * R8 + rr) << 11) + cg * KC2 + kc];
-        inv_rows<S2, KC2>(v, P.tw, 8 + G, q);
+            for (int kc = 0; kc < KC2; kc++) v[rr * KC2 + kc] = A::load_mid(dst[((size_t)(G * R8 + rr) << 11) + cg * KC2 + kc]);
+        inv_rows<A, S2, KC2>(v, P.tw, 8 + G, P.mc);
 #pragma unroll
         for (int rr = 0; rr < R8; rr++)
 #pragma unroll
@@ -305,113 +443,124 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_inv_hi_kernel(NttArgs A, Poly
         const u32 r0 = tid / CC, col = tid % CC;
 #pragma unroll
         for (int j = 0; j < 8; j++) v[j] = lds[(r0 + R8 * j) * CC + col];
-        inv_rows<3, 1>(v, P.tw, 1, q);
+        inv_rows<A, 3, 1>(v, P.tw, 1, P.mc);
 #pragma unroll
-        for (int j = 0; j < 8; j++)
-            dst[((size_t)(r0 + R8 * j) << 11) + col] = mul_shoup(v[j], P.mc.n_inv, P.mc.n_inv_sh, q);
+        for (int j = 0; j < 8; j++) dst[((size_t)(r0 + R8 * j) << 11) + col] = A::store_inv_final(v[j], P.mc);
     }
 }
 
-// ================================= rings below 2^11: one tile per poly =================================
+// ================================= rings below 2^11: one tile per poly (integer arithmetic) ==============
 template <bool INVERSE>
-__global__ __launch_bounds__(NTT_THREADS) void ntt_small_kernel(NttArgs A, PolyList pl) {
+__global__ __launch_bounds__(NTT_THREADS) void ntt_small_kernel(NttArgs args, PolyList pl) {
+    typedef ArithU64 A;
     __shared__ u64 lds[NTT_TILE];
     const u32 tid = threadIdx.x;
-    const PolyRef P = poly_ref(A, pl, blockIdx.y / pl.n, blockIdx.y % pl.n);
-    const u64 q = P.mc.q;
-    const u32 n = 1u << A.log_n;
+    const PolyRef<A> P = poly_ref<A>(args, pl, blockIdx.y / pl.n, blockIdx.y % pl.n);
+    const u32 n = 1u << args.log_n;
     for (u32 e = tid; e < n; e += NTT_THREADS) lds[e] = P.src[e];
     __syncthreads();
-    for (u32 st = 0; st < A.log_n; st++) {
-        const u32 r = INVERSE ? A.log_n - 1 - st : st;  // stage with 2^r groups
-        const u32 lt = A.log_n - 1 - r;                 // log2 of the pair distance
+    for (u32 st = 0; st < args.log_n; st++) {
+        const u32 r = INVERSE ? args.log_n - 1 - st : st;  // stage with 2^r groups
+        const u32 lt = args.log_n - 1 - r;                 // log2 of the pair distance
         for (u32 bf = tid; bf < n / 2; bf += NTT_THREADS) {
             const u32 i = bf >> lt;
             const u32 i0 = (i << (lt + 1)) + (bf & ((1u << lt) - 1)), i1 = i0 + (1u << lt);
             u64 x = lds[i0], y = lds[i1];
-            if (INVERSE) inv_bf(x, y, P.tw[(1u << r) + i], q); else fwd_bf(x, y, P.tw[(1u << r) + i], q);
+            if (INVERSE) A::inv_bf(x, y, P.tw[(1u << r) + i], P.mc); else A::fwd_bf(x, y, P.tw[(1u << r) + i], P.mc);
             lds[i0] = x;
             lds[i1] = y;
         }
         __syncthreads();
     }
-    for (u32 e = tid; e < n; e += NTT_THREADS)
-        P.dst[e] = INVERSE ? mul_shoup(lds[e], P.mc.n_inv, P.mc.n_inv_sh, q) : reduce_word(lds[e], P.mc);
+    for (u32 e = tid; e < n; e += NTT_THREADS) P.dst[e] = INVERSE ? A::store_inv_final(lds[e], P.mc) : A::store_fwd_final(lds[e], P.mc);
 }
 
-template <int LOG_HI>
-static void launch_hi(bool inverse, dim3 grid, hipStream_t st, const NttArgs& A, const PolyList& pl) {
-    if (inverse) hipLaunchKernelGGL(ntt_inv_hi_kernel<LOG_HI>, grid, dim3(NTT_THREADS), 0, st, A, pl);
-    else hipLaunchKernelGGL(ntt_fwd_hi_kernel<LOG_HI>, grid, dim3(NTT_THREADS), 0, st, A, pl);
+template <class A, int LOG_HI>
+static void launch_hi(bool inverse, dim3 grid, hipStream_t st, const NttArgs& args, const PolyList& pl) {
+    if (inverse) hipLaunchKernelGGL((ntt_inv_hi_kernel<A, LOG_HI>), grid, dim3(NTT_THREADS), 0, st, args, pl);
+    else hipLaunchKernelGGL((ntt_fwd_hi_kernel<A, LOG_HI>), grid, dim3(NTT_THREADS), 0, st, args, pl);
 }
 
-static void launch_hi_any(u32 log_hi, bool inverse, dim3 grid, hipStream_t st, const NttArgs& A, const PolyList& pl) {
+template <class A>
+static void launch_hi_any(u32 log_hi, bool inverse, dim3 grid, hipStream_t st, const NttArgs& args, const PolyList& pl) {
     switch (log_hi) {
-        case 1: launch_hi<1>(inverse, grid, st, A, pl); break;
-        case 2: launch_hi<2>(inverse, grid, st, A, pl); break;
-        case 3: launch_hi<3>(inverse, grid, st, A, pl); break;
-        case 4: launch_hi<4>(inverse, grid, st, A, pl); break;
-        case 5: launch_hi<5>(inverse, grid, st, A, pl); break;
-        default: launch_hi<6>(inverse, grid, st, A, pl); break;
+        case 1: launch_hi<A, 1>(inverse, grid, st, args, pl); break;
+        case 2: launch_hi<A, 2>(inverse, grid, st, args, pl); break;
+        case 3: launch_hi<A, 3>(inverse, grid, st, args, pl); break;
+        case 4: launch_hi<A, 4>(inverse, grid, st, args, pl); break;
+        case 5: launch_hi<A, 5>(inverse, grid, st, args, pl); break;
+        default: launch_hi<A, 6>(inverse, grid, st, args, pl); break;
     }
+}
+
+template <class A>
+static void launch_lo(bool inverse, dim3 grid, hipStream_t st, const NttArgs& args, const PolyList& pl) {
+    if (inverse) hipLaunchKernelGGL((ntt_inv_lo_kernel<A>), grid, dim3(NTT_THREADS), 0, st, args, pl);
+    else hipLaunchKernelGGL((ntt_fwd_lo_kernel<A>), grid, dim3(NTT_THREADS), 0, st, args, pl);
 }
 
 hipError_t launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, size_t src_bstride, u64* dst,
                       size_t dst_bstride, const PolyList& pl, u32 batch, hipStream_t st, const u64* const* src_ptrs) {
     if (pl.n == 0 || batch == 0) return hipSuccess;
     if (src_ptrs && batch > KS_MAX_BATCH) return hipErrorInvalidValue;
-    NttArgs A;
-    A.src = src;
-    A.dst = dst;
-    A.src_bstride = src_bstride;
-    A.dst_bstride = dst_bstride;
-    A.mc = c->d_mc;
-    A.tw = inverse ? c->d_itw : c->d_tw;
-    A.log_n = c->log_n;
-    A.log_lo = c->log_lo;
-    A.log_hi = c->log_hi;
-    A.last = 1;
-    A.batch = batch;
+    const bool f64 = c->ntt_f64;
+    NttArgs args;
+    args.src = src;
+    args.dst = dst;
+    args.src_bstride = src_bstride;
+    args.dst_bstride = dst_bstride;
+    args.mc = f64 ? (const void*)c->d_mcf : (const void*)c->d_mc;
+    args.tw = f64 ? (const void*)(inverse ? c->d_itwf : c->d_twf) : (const void*)(inverse ? c->d_itw : c->d_tw);
+    args.log_n = c->log_n;
+    args.log_lo = c->log_lo;
+    args.log_hi = c->log_hi;
+    args.first = 1;
+    args.last = 1;
+    args.batch = batch;
     {
         const u32 slices = pl.n << c->log_hi;
-        A.lo_group = 0;
+        args.lo_group = 0;
         for (u32 g = 64; g >= 8; g >>= 1)
-            if (slices % g == 0) { A.lo_group = g; break; }
+            if (slices % g == 0) { args.lo_group = g; break; }
     }
-    A.use_src_list = src_ptrs ? 1 : 0;
-    for (u32 b = 0; b < KS_MAX_BATCH; b++) A.src_list.p[b] = (src_ptrs && b < batch) ? src_ptrs[b] : nullptr;
+    args.use_src_list = src_ptrs ? 1 : 0;
+    for (u32 b = 0; b < KS_MAX_BATCH; b++) args.src_list.p[b] = (src_ptrs && b < batch) ? src_ptrs[b] : nullptr;
     const u32 polys = pl.n * batch;
     const dim3 block(NTT_THREADS);
     const double pass_bytes = 16.0 * polys * c->N;
     if (c->log_n < CKKS_TILE_LOG) {
         ProfScope ps__(c, inverse ? K_NTT_INV_LO : K_NTT_FWD_LO, st, pass_bytes, 0.5 * polys * c->N * c->log_n);
-        if (inverse) hipLaunchKernelGGL(ntt_small_kernel<true>, dim3(1, polys), block, 0, st, A, pl);
-        else hipLaunchKernelGGL(ntt_small_kernel<false>, dim3(1, polys), block, 0, st, A, pl);
+        if (inverse) hipLaunchKernelGGL(ntt_small_kernel<true>, dim3(1, polys), block, 0, st, args, pl);
+        else hipLaunchKernelGGL(ntt_small_kernel<false>, dim3(1, polys), block, 0, st, args, pl);
         return hipGetLastError();
     }
     const dim3 grid(c->N >> CKKS_TILE_LOG, polys);  // hi pass: one workgroup per 2^11 points
     const u32 slices = pl.n << c->log_hi;
-    const dim3 grid_lo = A.lo_group ? dim3(A.lo_group, batch, slices / A.lo_group) : dim3(batch, slices);  // see lo_tile()
+    const dim3 grid_lo = args.lo_group ? dim3(args.lo_group, batch, slices / args.lo_group) : dim3(batch, slices);  // see lo_tile()
     const double lo_ops = 0.5 * polys * c->N * c->log_lo, hi_ops = 0.5 * polys * c->N * c->log_hi;
     // the second pass of either direction continues in place on dst
-    NttArgs B = A;
-    B.src = dst;
-    B.src_bstride = dst_bstride;
-    B.use_src_list = 0;
+    NttArgs second = args;
+    second.src = dst;
+    second.src_bstride = dst_bstride;
+    second.use_src_list = 0;
+    second.first = 0;
     PolyList pd = pl;
     for (u32 i = 0; i < pl.n; i++) pd.spos[i] = pl.dpos[i];
+    auto hi = [&](const NttArgs& a, const PolyList& l) { if (f64) launch_hi_any<ArithF64>(c->log_hi, inverse, grid, st, a, l); else launch_hi_any<ArithU64>(c->log_hi, inverse, grid, st, a, l); };
+    auto lo = [&](const NttArgs& a, const PolyList& l) { if (f64) launch_lo<ArithF64>(inverse, grid_lo, st, a, l); else launch_lo<ArithU64>(inverse, grid_lo, st, a, l); };
     if (!inverse) {
         if (c->log_hi > 0) {
-            { ProfScope ps__(c, K_NTT_FWD_HI, st, pass_bytes, hi_ops); launch_hi_any(c->log_hi, false, grid, st, A, pl); }
-            { ProfScope ps__(c, K_NTT_FWD_LO, st, pass_bytes, lo_ops); hipLaunchKernelGGL(ntt_fwd_lo_kernel, grid_lo, block, 0, st, B, pd); }
+            args.last = 0;
+            { ProfScope ps__(c, K_NTT_FWD_HI, st, pass_bytes, hi_ops); hi(args, pl); }
+            { ProfScope ps__(c, K_NTT_FWD_LO, st, pass_bytes, lo_ops); lo(second, pd); }
         } else {
             ProfScope ps__(c, K_NTT_FWD_LO, st, pass_bytes, lo_ops);
-            hipLaunchKernelGGL(ntt_fwd_lo_kernel, grid_lo, block, 0, st, A, pl);
+            lo(args, pl);
         }
     } else {
-        A.last = c->log_hi == 0;
-        { ProfScope ps__(c, K_NTT_INV_LO, st, pass_bytes, lo_ops); hipLaunchKernelGGL(ntt_inv_lo_kernel, grid_lo, block, 0, st, A, pl); }
-        if (c->log_hi > 0) { ProfScope ps__(c, K_NTT_INV_HI, st, pass_bytes, hi_ops); launch_hi_any(c->log_hi, true, grid, st, B, pd); }
+        args.last = c->log_hi == 0;
+        { ProfScope ps__(c, K_NTT_INV_LO, st, pass_bytes, lo_ops); lo(args, pl); }
+        if (c->log_hi > 0) { ProfScope ps__(c, K_NTT_INV_HI, st, pass_bytes, hi_ops); hi(second, pd); }
     }
     return hipGetLastError();
 }
