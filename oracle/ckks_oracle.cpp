@@ -338,6 +338,56 @@ void orc_moddown(void* h, int level, const u64* v, u64* u) {
     }
 }
 
+// Exact-up-to-rounding division by the product D of a set of dropped limbs, written from its definition
+// (ModDown is the case "drop the special primes", rescaling the case "drop q_level"; dropping both at
+// once divides by P * q_level with a single rounding).  v: [n_keep + n_drop][N] in NTT form, the kept
+// limbs first; limb t is modulo moduli[keep_idx[t]] resp. moduli[drop_idx[t - n_keep]].
+//   z_a = [v_a * (D/d_a)^-1] mod d_a  centred;   w_i = sum_a z_a * [D/d_a] mod q_i;   out_i = (v_i - w_i) / D mod q_i.
+void orc_divide_by_limbs(void* h, const int* keep_idx, int n_keep, const int* drop_idx, int n_drop, const u64* v, u64* out) {
+    Ctx* c = (Ctx*)h;
+    int N = c->N;
+    std::vector<u64> z((size_t)n_drop * N);
+#pragma omp parallel for
+    for (int a = 0; a < n_drop; a++) {
+        u64 da = c->mod[drop_idx[a]];
+        u64 dhat = 1;
+        for (int b = 0; b < n_drop; b++) if (b != a) dhat = mulmod(dhat, c->mod[drop_idx[b]] % da, da);
+        u64 dhat_inv = invmod(dhat, da);
+        u64* za = z.data() + (size_t)a * N;
+        memcpy(za, v + (size_t)(n_keep + a) * N, sizeof(u64) * N);
+        orc_ntt_inv(h, drop_idx[a], za);
+        for (int x = 0; x < N; x++) za[x] = mulmod(za[x], dhat_inv, da);
+    }
+#pragma omp parallel for
+    for (int i = 0; i < n_keep; i++) {
+        u64 qi = c->mod[keep_idx[i]];
+        std::vector<u64> dhat_i(n_drop);
+        u64 D_i = 1;
+        for (int a = 0; a < n_drop; a++) {
+            u64 w = 1;
+            for (int b = 0; b < n_drop; b++) if (b != a) w = mulmod(w, c->mod[drop_idx[b]] % qi, qi);
+            dhat_i[a] = w;
+            D_i = mulmod(D_i, c->mod[drop_idx[a]] % qi, qi);
+        }
+        u64 Dinv = invmod(D_i, qi);
+        std::vector<u64> w(N);
+        for (int x = 0; x < N; x++) {
+            u64 acc = 0;
+            for (int a = 0; a < n_drop; a++) {
+                u64 da = c->mod[drop_idx[a]], za = z[(size_t)a * N + x];
+                u64 zi = za % qi;
+                if (za > da / 2) zi = submod(zi, da % qi, qi);     // centred z_a reduced modulo q_i
+                acc = addmod(acc, mulmod(zi, dhat_i[a], qi), qi);
+            }
+            w[x] = acc;
+        }
+        orc_ntt_fwd(h, keep_idx[i], w.data());
+        const u64* vi = v + (size_t)i * N;
+        u64* oi = out + (size_t)i * N;
+        for (int x = 0; x < N; x++) oi[x] = mulmod(submod(vi[x], w[x], qi), Dinv, qi);
+    }
+}
+
 // KeySwitch(c, key): [level+1][N] -> out[2][level+1][N] with out0 + out1*s ~ c * s'.
 void orc_keyswitch(void* h, int level, const u64* cin, const u64* key, u64* out) {
     Ctx* c = (Ctx*)h;

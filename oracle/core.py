@@ -180,6 +180,22 @@ class Oracle:
         self.lib.orc_moddown(self.h, level, _p(v), _p(out))
         return out
 
+    def divide_by_limbs(self, v, keep_idx: Sequence[int], drop_idx: Sequence[int]) -> np.ndarray:
+        """v [len(keep)+len(drop)][N] (kept limbs first) divided by the product of the dropped moduli, rounded
+        (centred remainder, error below len(drop)/2): ModDown and rescale are special cases."""
+        v = _u64(v)
+        keep = np.array(keep_idx, dtype=np.int32)
+        drop = np.array(drop_idx, dtype=np.int32)
+        assert v.shape == (len(keep) + len(drop), self.N)
+        out = np.empty((len(keep), self.N), dtype=np.uint64)
+        self.lib.orc_divide_by_limbs(self.h, _p(keep), len(keep), _p(drop), len(drop), _p(v), _p(out))
+        return out
+
+    def moddown_rescale(self, v, level: int) -> np.ndarray:
+        """ModDown and rescale in one step: v on the extended basis q_0..q_level, p_0.. divided by P * q_level
+        with a single rounding; result [level][N]."""
+        return self.divide_by_limbs(v, list(range(level)), [level] + list(range(self.num_q, self.M)))
+
     def keyswitch(self, c, key, level: int) -> np.ndarray:
         c, key = _u64(c), _u64(key)
         assert c.shape == (level + 1, self.N) and key.shape == (self.dnum, 2, self.M, self.N)
@@ -509,7 +525,8 @@ class Oracle:
         return row
 
     def he_conv_deferred(self, cts: Sequence[np.ndarray], level: int, width: int, rot_keys: Dict[int, np.ndarray],
-                         M_ext: np.ndarray, w_int: np.ndarray, out_channels: Optional[Iterable[int]] = None) -> Dict[int, np.ndarray]:
+                         M_ext: np.ndarray, w_int: np.ndarray, out_channels: Optional[Iterable[int]] = None,
+                         merged: bool = False) -> Dict[int, np.ndarray]:
         """The batched convolution layer (Eqs. 10-11) with one division by P per OUTPUT channel
         instead of one per rotation:
             out_o = Rescale( ModDown( sum_c sum_tap pt[o,c,tap] (.) X_tap(ct_c) ) ),
@@ -527,8 +544,11 @@ class Oracle:
                     pts.append(self.scalar_mul_ext(M_ext[t], self.scalar_residues_ext(int(w_int[o, c, t]), level), level))
                     terms.append(aligned[c][t])
             acc = self.mac_ext(pts, terms, level)
-            u = np.stack([self.moddown(acc[0], level), self.moddown(acc[1], level)])
-            outs[o] = self.rescale(u, level)
+            if merged:   # ModDown and rescale as one division by P * q_level
+                outs[o] = np.stack([self.moddown_rescale(acc[0], level), self.moddown_rescale(acc[1], level)])
+            else:
+                u = np.stack([self.moddown(acc[0], level), self.moddown(acc[1], level)])
+                outs[o] = self.rescale(u, level)
         return outs
 
     def he_conv(self, cts: Sequence[np.ndarray], level: int, width: int, rot_keys: Dict[int, np.ndarray],
@@ -578,6 +598,48 @@ class Oracle:
                 t = self.rotate(t, level, -i * sts, rot_keys[-i * sts], True)
             total = t if total is None else self.add(total, t, level)
         return self.rescale(total, level)
+
+    # ------------------------------------------- ciphertext product with the merged division
+    def ctct_mul_relin_rescale(self, a, b, rlk, level: int, addend=None) -> np.ndarray:
+        """Rescale(a*b + addend) with the relinearisation's division by P and the rescale's division by
+        q_level merged into one (a single rounding, 48 fewer limb transforms at 24 limbs):
+            (d0, d1, d2) = (a0 b0, a0 b1 + a1 b0, a1 b1),   v = < ModUp(d2), rlk >  on Q_level P,
+            out_c = (v_c + P * (d_c + addend_c)) / (P * q_level),   c = 0, 1.
+        a, b, addend: [2][level+1][N]; result [2][level][N]."""
+        a, b = _u64(a), _u64(b)
+        L1 = level + 1
+        idx = list(range(L1))
+        d0 = self.mul(a[0], b[0], idx)
+        d1 = self.add(self.mul(a[0], b[1], idx), self.mul(a[1], b[0], idx), level)
+        d2 = self.mul(a[1], b[1], idx)
+        if addend is not None:
+            addend = _u64(addend)
+            d0, d1 = self.add(d0, addend[0], level), self.add(d1, addend[1], level)
+        v = self.key_inner(self.modup(d2, level), rlk, level)
+        Pres = self.special_product_residues(level)[:L1]
+        out = []
+        for comp, dpart in enumerate((d0, d1)):
+            vc = v[comp].copy()
+            vc[:L1] = self.add(vc[:L1], self.scalar_mul(dpart, Pres, level), level)
+            out.append(self.moddown_rescale(vc, level))
+        return np.stack(out)
+
+    def poly_activation_merged(self, x, level: int, k: Sequence[int], rlk) -> np.ndarray:
+        """The degree-7 activation of poly_activation with every relinearise-then-rescale pair replaced by
+        the merged division (same levels, scales and integer scalars; other residues: one rounding per product)."""
+        k1, k3, k5, k7 = [int(v) for v in k]
+        x = _u64(x)
+        x2 = self.ctct_mul_relin_rescale(x, x, rlk, level)                                       # level-1
+        xd1 = self.drop_to_level(x, level - 1)
+        x3 = self.ctct_mul_relin_rescale(x2, xd1, rlk, level - 1)                                # level-2
+        x4 = self.ctct_mul_relin_rescale(x2, x2, rlk, level - 1)                                 # level-2
+        l2, l3 = level - 2, level - 3
+        Bp = self.add(self.scalar_mul(self.drop_to_level(x, l2), self.scalar_residues(k5, l2), l2),
+                      self.scalar_mul(x3, self.scalar_residues(k7, l2), l2), l2)
+        B = self.rescale(Bp, l2)                                                                 # level-3
+        A = self.add(self.scalar_mul(self.drop_to_level(x, l3), self.scalar_residues(k1, l3), l3),
+                     self.scalar_mul(self.drop_to_level(x3, l3), self.scalar_residues(k3, l3), l3), l3)
+        return self.ctct_mul_relin_rescale(self.drop_to_level(x4, l3), B, rlk, l3, addend=A)     # level-4
 
     # ----------------------------------------------------------------------- activation
     def act_schedule(self, level: int, scale: float) -> dict:

@@ -293,3 +293,45 @@ def test_encrypted_activation_matches_float():
     assert out.shape == (2, plan["out_level"] + 1, o.N)
     got = o.decrypt(out, plan["out_level"], s_ntt, plan["out_scale"])
     assert np.abs(got - activation_reference(x)).max() < 1e-3
+
+
+def test_merged_division_product_and_activation_match_float():
+    """Rescale(a*b + addend) with one division by P*q_level: decrypts to the slot-wise product plus the
+    addend, agrees with the two-step version up to rounding noise, and the activation built on it
+    matches the float64 polynomial."""
+    wl = CONFIGS["small_block"]
+    p = wl.params()
+    o = Oracle(p)
+    level = p.num_q - 1
+    s, s_ntt = o.gen_secret(11000)
+    rlk = o.gen_relin_key(s_ntt, 11001)
+    rng = np.random.default_rng(8)
+    xa, xb, xc = (rng.uniform(-1, 1, o.n) for _ in range(3))
+    scale = 2.0 ** 50
+    a, b = o.encrypt(xa, scale, level, s_ntt, 11002), o.encrypt(xb, scale, level, s_ntt, 11003)
+    # an addend at the product's scale 2^100: an encryption at 2^50 times the integer 2^50
+    add = o.scalar_mul(o.encrypt(xc, scale, level, s_ntt, 11004), o.scalar_residues(2 ** 50, level), level)
+    out = o.ctct_mul_relin_rescale(a, b, rlk, level, addend=add)
+    assert out.shape == (2, level, o.N)
+    out_scale = scale * scale / p.moduli[level]
+    assert np.abs(o.decrypt(out, level - 1, s_ntt, out_scale) - (xa * xb + xc)).max() < 1e-6
+    two_step = o.rescale(o.add(o.ctct_mul_relin(a, b, rlk, level), add, level), level)
+    assert np.abs(o.decrypt(out, level - 1, s_ntt, out_scale) - o.decrypt(two_step, level - 1, s_ntt, out_scale)).max() < 1e-7
+    assert not np.array_equal(out, two_step)
+    plan = o.act_schedule(level, scale)
+    y = o.poly_activation_merged(a, level, plan["k"], rlk)
+    assert y.shape == (2, plan["out_level"] + 1, o.N)
+    assert np.abs(o.decrypt(y, plan["out_level"], s_ntt, plan["out_scale"]) - activation_reference(xa)).max() < 1e-3
+
+
+def test_he_conv_deferred_with_merged_division_decrypts_to_float_conv():
+    wl, p, o, level, s, s_ntt, img, w, scale, cts, keys = _conv_setup("small_conv", 12000)
+    delta_m = 2.0 ** 28
+    M_ext, w_int = o.conv_operands_ext(w, wl.height, wl.width, wl.batch, level, delta_m, p.moduli[level] / delta_m)
+    outs = o.he_conv_deferred(cts, level, wl.width, keys, M_ext, w_int, merged=True)
+    two = o.he_conv_deferred(cts, level, wl.width, keys, M_ext, w_int)
+    want = conv2d_reference(img, w)
+    for oc, ct in outs.items():
+        z = o.decrypt(ct, level - 1, s_ntt, scale)
+        assert np.abs(o.unpack_channel(z, wl.batch, wl.height, wl.width) - want[:, oc]).max() < 1e-4
+        assert np.abs(z - o.decrypt(two[oc], level - 1, s_ntt, scale)).max() < 1e-6

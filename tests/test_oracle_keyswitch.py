@@ -259,3 +259,44 @@ def test_samplers():
     u2 = np.empty_like(u)
     o.lib.orc_sample_uniform(C.c_uint64(3), C.c_uint64(q), len(u), u2.ctypes.data_as(C.c_void_p))
     assert np.array_equal(u, u2)
+
+
+# ------------------------------------------------------------------ merged division (ModDown + rescale)
+def test_divide_by_limbs_reduces_to_moddown_and_to_rescale(tiny_params):
+    """Dropping the special primes is ModDown; dropping q_level is the rescale: same residues as the
+    dedicated routines (which have their own big-integer pins)."""
+    o = Oracle(tiny_params)
+    rng = np.random.default_rng(80)
+    level = 2
+    ext = o.ext_moduli_idx(level)
+    v = np.stack([rng.integers(0, o.moduli[t], o.N, dtype=np.uint64) for t in ext])
+    assert np.array_equal(o.divide_by_limbs(v, list(range(level + 1)), list(range(o.num_q, o.M))), o.moddown(v, level))
+    ct = np.stack([v[:level + 1], v[:level + 1][::-1].copy() % np.array([[o.moduli[i]] for i in range(level + 1)], dtype=np.uint64)])
+    got = np.stack([o.divide_by_limbs(ct[c], list(range(level)), [level]) for c in range(2)])
+    assert np.array_equal(got, o.rescale(ct, level))
+
+
+def test_moddown_rescale_is_the_rounded_quotient(tiny_params):
+    """Big-integer pin: the result times P*q_level differs from the input by less than (k+1)/2 * P*q_level
+    on every coefficient (CRT over the kept limbs, centred)."""
+    o = Oracle(tiny_params)
+    rng = np.random.default_rng(81)
+    level = 2
+    ext = o.ext_moduli_idx(level)
+    mods_ext = [o.moduli[t] for t in ext]
+    v = np.stack([rng.integers(0, q, o.N, dtype=np.uint64) for q in mods_ext])
+    out = o.moddown_rescale(v, level)
+    assert out.shape == (level, o.N)
+    v_coef = np.stack([o.ntt_inv(v[e], ext[e]) for e in range(len(ext))])
+    out_coef = np.stack([o.ntt_inv(out[i], i) for i in range(level)])
+    D = o.moduli[level]
+    for t in range(o.num_q, o.M):
+        D *= o.moduli[t]
+    Qkeep = prod(o.moduli[:level])
+    Qall = prod(mods_ext)
+    for x in range(o.N):
+        V = centred(crt([v_coef[e][x] for e in range(len(ext))], mods_ext), Qall)
+        U = crt([out_coef[i][x] for i in range(level)], o.moduli[:level])
+        # U = round(V / D) modulo Qkeep, up to the conversion error
+        err = centred(U * D - V, Qkeep * D)
+        assert abs(err) <= (o.num_p + 1) * D // 2 + D, (x, err)
