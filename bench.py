@@ -55,9 +55,12 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="cfg5_resnet20_stage3")
-    ap.add_argument("--alignment", default="deferred", choices=["direct", "four_keys", "deferred"],
+    ap.add_argument("--alignment", default="deferred_merged", choices=["direct", "four_keys", "deferred", "deferred_merged"],
                     help="convolution schedule: eight hoisted rotations with one ModDown each (direct), the paper's four-key "
-                         "two-stage alignment, or one ModDown per output channel after the sum (deferred, the default)")
+                         "two-stage alignment, one ModDown per output channel after the sum (deferred), or that ModDown merged "
+                         "with the rescale (deferred_merged, the default)")
+    ap.add_argument("--two-step-activation", action="store_true",
+                    help="activation with separate ModDown and rescale after every product (default: merged into one division)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--no-kernel-timing", action="store_true", help="skip the per-kernel event pass")
     ap.add_argument("--no-microbench", action="store_true", help="skip the rotation and NTT microbenchmarks")
@@ -67,7 +70,7 @@ def parse_args():
     return ap.parse_args()
 
 
-def cpu_baseline(wl, params, alignment):
+def cpu_baseline(wl, params, alignment, act_merged):
     """Times the CPU oracle on a bounded sample of the same workload and schedule and extrapolates to one step."""
     import numpy as np
     from oracle import Oracle
@@ -75,7 +78,8 @@ def cpu_baseline(wl, params, alignment):
     orc = Oracle(params)
     level = params.num_q - 1
     q = params.moduli
-    deferred = alignment == "deferred"
+    deferred = alignment.startswith("deferred")
+    merged = alignment == "deferred_merged"
     ct = uniform_residues((2, level + 1, orc.N), q[:level + 1], "cpu_ct")
     key = uniform_residues((params.dnum, 2, orc.M, orc.N), q, "cpu_key")
     offs = conv_tap_offsets(wl.width)
@@ -94,12 +98,15 @@ def cpu_baseline(wl, params, alignment):
     acc = orc.mac_ext(pts, aligned, level) if deferred else orc.ptct_mac(pts, aligned, level)
     t_mac = time.perf_counter() - t0                        # 9 taps of one (input, output) channel pair
     t0 = time.perf_counter()
-    if deferred:
-        acc = np.stack([orc.moddown(acc[0], level), orc.moddown(acc[1], level)])
-    x = orc.rescale(acc, level)
+    if merged:
+        x = np.stack([orc.moddown_rescale(acc[0], level), orc.moddown_rescale(acc[1], level)])
+    else:
+        if deferred:
+            acc = np.stack([orc.moddown(acc[0], level), orc.moddown(acc[1], level)])
+        x = orc.rescale(acc, level)
     t_out = time.perf_counter() - t0                        # one output channel: (ModDown and) rescale
     t0 = time.perf_counter()
-    orc.poly_activation(x, level - 1, (3 << 40, -(5 << 40), 7 << 40, -(9 << 40)), key)
+    (orc.poly_activation_merged if act_merged else orc.poly_activation)(x, level - 1, (3 << 40, -(5 << 40), 7 << 40, -(9 << 40)), key)
     t_act = time.perf_counter() - t0
     step = wl.c_in * t_align + wl.c_in * wl.c_out * t_mac + wl.c_out * (t_out + t_act)
     cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
@@ -136,9 +143,12 @@ def main():
     keys = [hx.ckks_key_load(ctx, hx.from_host(uniform_residues((params.dnum, 2, M, N), q, "rk%d" % t)),
                              hx.ckks_galois_element(ctx, off)) if off else None for t, off in enumerate(offs)]
     rlk = hx.ckks_key_load(ctx, hx.from_host(uniform_residues((params.dnum, 2, M, N), q, "rlk")), 0)
-    mode = {"direct": hx.HE_CONV_ALIGN_DIRECT, "four_keys": hx.HE_CONV_ALIGN_FOUR_KEYS, "deferred": hx.HE_CONV_DEFERRED_MODDOWN}[args.alignment]
+    mode = {"direct": hx.HE_CONV_ALIGN_DIRECT, "four_keys": hx.HE_CONV_ALIGN_FOUR_KEYS, "deferred": hx.HE_CONV_DEFERRED_MODDOWN,
+            "deferred_merged": hx.HE_CONV_DEFERRED_MERGED}[args.alignment]
+    deferred = args.alignment.startswith("deferred")
+    act_merged = not args.two_step_activation
     # operands of the multiply-accumulate live on the extended basis (q_0..q_level, p_0..) in the deferred schedule
-    q_mac = (q[:level + 1] + q[params.num_q:]) if args.alignment == "deferred" else q[:level + 1]
+    q_mac = (q[:level + 1] + q[params.num_q:]) if deferred else q[:level + 1]
     masks = hx.from_host(uniform_residues((9, len(q_mac), N), q_mac, "masks"))
     w_res = hx.from_host(uniform_residues((wl.c_out * wl.c_in * 9, len(q_mac), 1), q_mac, "w").reshape(wl.c_out, wl.c_in, 9, len(q_mac)))
     conv_out = [hx.empty(2, level, N) for _ in range(wl.c_out)]
@@ -153,7 +163,7 @@ def main():
     def step():
         hx.he_conv_batched(ctx, wl.height, wl.width, wl.batch, level, ins, keys, masks, w_res, wl.c_out, outs=conv_out, ws=ws,
                            alignment=mode)
-        hx.he_poly_act_deg7(ctx, conv_out, level - 1, k_act, rlk, outs=act_out, ws=ws)
+        hx.he_poly_act_deg7(ctx, conv_out, level - 1, k_act, rlk, outs=act_out, ws=ws, merged=act_merged)
 
     for _ in range(args.warmup):
         step()
@@ -178,7 +188,7 @@ def main():
         "config": {"workload": wl.name, "log_n": params.log_n, "limbs": params.num_q, "special_primes": params.num_p,
                    "dnum": params.dnum, "c_in": wl.c_in, "c_out": wl.c_out, "image": "%dx%d" % (wl.height, wl.width),
                    "batch": wl.batch, "rotations_per_step": n_rot, "keyswitches_per_step": n_keyswitch,
-                   "conv_schedule": args.alignment},
+                   "conv_schedule": args.alignment, "activation": "merged_division" if act_merged else "two_step"},
     }
 
     # per-kernel event timing over one more step (every launch bracketed on its own stream)
@@ -233,7 +243,7 @@ def main():
         result["calibration_copy_bytes_each_way"] = 2 * (level + 1) * N * 8
     if args.no_microbench:
         if not args.no_cpu_baseline:
-            result["cpu_baseline"] = cpu_baseline(wl, params, args.alignment)
+            result["cpu_baseline"] = cpu_baseline(wl, params, args.alignment, act_merged)
         print(json.dumps(result))
         return
     # ---- the two microbenchmark shapes, reported next to the headline value ------------------------
@@ -297,7 +307,7 @@ def main():
     result["ntt_butterflies_per_s"] = result["ntt_limbs_per_s"] * (N // 2) * p2.log_n
 
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(wl, params, args.alignment)
+        result["cpu_baseline"] = cpu_baseline(wl, params, args.alignment, act_merged)
     print(json.dumps(result))
 
 

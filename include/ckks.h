@@ -156,7 +156,7 @@ typedef enum he_conv_alignment {
                                    Rot(in,+1), then Rot(.,-W) and Rot(.,+W) of C^-1, in, C^+1; only the keys
                                    of -1, +1, -W, +W (rot_keys entries 3, 5, 1, 7) are read; three
                                    decompositions per input; half the resident key bytes */
-    HE_CONV_DEFERRED_MODDOWN = 2/* eight direct rotations as in DIRECT, but the division by P that ends each
+    HE_CONV_DEFERRED_MODDOWN = 2,/* eight direct rotations as in DIRECT, but the division by P that ends each
                                    key switch is taken once per OUTPUT channel, after the sum of Eq. 11:
                                      X_tap(in) = (P * sigma_g(c0) + v_0, v_1),  v = <sigma_g(ModUp(c1)), key_g>
                                      out_o = Rescale( ModDown( sum_c sum_tap pt[o,c,tap] (.) X_tap(in_c) ) )
@@ -164,6 +164,9 @@ typedef enum he_conv_alignment {
                                    d_tap_masks is uint64[9][level+1+num_p][N] and d_w_res is
                                    uint64[C_out][C_in][9][level+1+num_p] (residues modulo the special primes
                                    appended); C_out ModDowns instead of 8*C_in, one rounding per output */
+    HE_CONV_DEFERRED_MERGED = 3/* as DEFERRED_MODDOWN, and the ModDown of every sum is merged with its rescale: one
+                                   division by P * q_level (dropped limbs q_level, p_0..p_{k-1}), one rounding, 48
+                                   fewer limb transforms per output at 24 limbs */
 } he_conv_alignment;
 
 typedef struct he_conv_desc {
@@ -200,10 +203,13 @@ int he_accumulator_merge(const ckks_ctx* ctx, const uint64_t* const* h_d_cts, ui
  * tracks scales; the same four for every channel).  h_d_x: n_ct device pointers uint64[2][level+1][N],
  * level >= 4; h_d_out: n_ct device pointers uint64[2][level-3][N].  Channels are processed in
  * batches that share one pass over the relinearisation key; workspace from
- * ckks_workspace_bytes(ctx, CKKS_OP_POLY_ACT, level, n_ct). */
+ * ckks_workspace_bytes(ctx, CKKS_OP_POLY_ACT, level, n_ct).
+ * merged_division != 0: every relinearise-then-rescale pair is one division by P * q_level instead of
+ * two (the tensor product's d0, d1, and for y the linear part, enter the extended basis as P times
+ * themselves before the division): same levels and scales, one rounding per product, other residues. */
 int he_poly_act_deg7(const ckks_ctx* ctx, const uint64_t* const* h_d_x, uint32_t n_ct, uint32_t level,
-                     const int64_t* h_k, const ckks_key* rlk, uint64_t* const* h_d_out, void* d_ws,
-                     size_t ws_bytes, void* stream);
+                     const int64_t* h_k, const ckks_key* rlk, int merged_division, uint64_t* const* h_d_out,
+                     void* d_ws, size_t ws_bytes, void* stream);
 
 /* Optional per-kernel timing, for benchmarks (not part of the paper's method; callers that measure).
  * Between ckks_prof_begin and ckks_prof_end every launch of a kernel class whose bit is set in

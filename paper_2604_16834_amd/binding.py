@@ -35,6 +35,7 @@ CKKS_OP_POLY_ACT = 5
 HE_CONV_ALIGN_DIRECT = 0
 HE_CONV_ALIGN_FOUR_KEYS = 1
 HE_CONV_DEFERRED_MODDOWN = 2
+HE_CONV_DEFERRED_MERGED = 3
 
 EXPORTS = (
     "ckks_ctx_create", "ckks_ctx_destroy", "ckks_last_error_string", "ckks_workspace_bytes",
@@ -91,7 +92,7 @@ def _bind(path: str):
     lib.he_conv_workspace_bytes.argtypes = [vp, C.POINTER(_ConvDesc)]
     lib.he_conv_workspace_bytes.restype = sz
     lib.he_conv_batched.argtypes = [vp, C.POINTER(_ConvDesc), C.POINTER(vp), C.POINTER(vp), vp, vp, C.POINTER(vp), vp, sz, vp]
-    lib.he_poly_act_deg7.argtypes = [vp, C.POINTER(vp), u32, u32, C.POINTER(C.c_int64), vp, C.POINTER(vp), vp, sz, vp]
+    lib.he_poly_act_deg7.argtypes = [vp, C.POINTER(vp), u32, u32, C.POINTER(C.c_int64), vp, i32, C.POINTER(vp), vp, sz, vp]
     lib.he_accumulator_workspace_bytes.argtypes = [vp, u32, u32]
     lib.he_accumulator_workspace_bytes.restype = sz
     lib.he_accumulator_merge.argtypes = [vp, C.POINTER(vp), u32, u32, u32, vp, C.POINTER(vp), vp, vp, sz, vp]
@@ -313,15 +314,16 @@ def he_conv_batched(ctx: Context, height: int, width: int, batch: int, level: in
                     outs: Optional[List[torch.Tensor]] = None, ws: Optional[torch.Tensor] = None, stream=None,
                     alignment: int = HE_CONV_ALIGN_DIRECT) -> List[torch.Tensor]:
     """alignment: HE_CONV_ALIGN_DIRECT (eight hoisted rotations), HE_CONV_ALIGN_FOUR_KEYS (the paper's two-stage
-    alignment with four keys) or HE_CONV_DEFERRED_MODDOWN (one division by P per output channel).
+    alignment with four keys), HE_CONV_DEFERRED_MODDOWN (one division by P per output channel) or
+    HE_CONV_DEFERRED_MERGED (that division merged with the rescale).
     ins: C_in tensors [2][level+1][N]; rot_keys: nine entries in tap order (centre ignored);
     tap_masks [9][L][N]; w_res [C_out][C_in][9][L] residues of the integer weights, L = level+1 limbs
-    (level+1+num_p, the extended basis, for HE_CONV_DEFERRED_MODDOWN)."""
+    (level+1+num_p, the extended basis, for the two deferred schedules)."""
     c_in = len(ins)
     L1 = level + 1
     if len(rot_keys) != 9:
         raise ValueError("nine rotation-key entries expected (row-major taps, centre may be None)")
-    LM = L1 + ctx.num_p if alignment == HE_CONV_DEFERRED_MODDOWN else L1
+    LM = L1 + ctx.num_p if alignment in (HE_CONV_DEFERRED_MODDOWN, HE_CONV_DEFERRED_MERGED) else L1
     if tap_masks.numel() != 9 * LM * ctx.N or w_res.numel() != c_out * c_in * 9 * LM:
         raise ValueError("tap_masks must be [9][L][N] and w_res [C_out][C_in][9][L], L = %d limbs" % LM)
     for t in ins:
@@ -342,8 +344,10 @@ def he_conv_batched(ctx: Context, height: int, width: int, batch: int, level: in
 
 
 def he_poly_act_deg7(ctx: Context, xs: Sequence[torch.Tensor], level: int, k: Sequence[int], rlk: Key,
-                     outs: Optional[List[torch.Tensor]] = None, ws: Optional[torch.Tensor] = None, stream=None) -> List[torch.Tensor]:
-    """xs: channel ciphertexts [2][level+1][N]; returns one [2][level-3][N] per channel."""
+                     outs: Optional[List[torch.Tensor]] = None, ws: Optional[torch.Tensor] = None, stream=None,
+                     merged: bool = False) -> List[torch.Tensor]:
+    """xs: channel ciphertexts [2][level+1][N]; returns one [2][level-3][N] per channel.
+    merged: every relinearise-then-rescale pair as one division by P*q_level."""
     n = len(xs)
     if n == 0 or len(k) != 4:
         raise ValueError("need at least one ciphertext and four integers k")
@@ -359,7 +363,7 @@ def he_poly_act_deg7(ctx: Context, xs: Sequence[torch.Tensor], level: int, k: Se
     ka = (C.c_int64 * 4)(*[int(v) for v in k])
     xa = _ptr_array([_ptr(x) for x in xs])
     oa = _ptr_array([_ptr(o) for o in outs])
-    ctx._check(_lib.he_poly_act_deg7(ctx.handle, xa, n, level, ka, rlk.handle if rlk else None, oa, _ptr(ws),
+    ctx._check(_lib.he_poly_act_deg7(ctx.handle, xa, n, level, ka, rlk.handle if rlk else None, int(bool(merged)), oa, _ptr(ws),
                                      ws.numel() * ws.element_size(), _stream(stream)))
     return outs
 

@@ -118,12 +118,24 @@ int run_modup(const ckks_ctx* c, u32 level, const u64* const* srcs, u32 n, const
 
 // ModDown of the n inner products sitting in ws.v: one pass of each kernel over the whole batch.
 // items[r] says what is added to / multiplied into the r-th result and where it goes ([2][level+1][N]).
-int run_moddown(const ckks_ctx* c, u32 level, const KsWs& ws, u32 n, const FinalItem* items, hipStream_t st) {
+// merged: the division is by P*q_level (ModDown and rescale in one): the dropped limbs are position
+// level and the special primes, the results are [2][level][N].
+int run_moddown(const ckks_ctx* c, u32 level, const KsWs& ws, u32 n, const FinalItem* items, hipStream_t st, bool merged = false) {
     const u32 L1 = level + 1, E = c->ext_limbs(level), k = c->num_p;
+    if (merged) {
+        PolyList dl = range_list(level, k + 1, c->num_q - 1);  // positions level.. ; moduli fixed up below
+        dl.mod[0] = (unsigned char)level;
+        for (u32 a = 1; a <= k; a++) dl.mod[a] = (unsigned char)(c->num_q + a - 1);
+        HIP_TRY(launch_ntt(c, true, ws.v, E, ws.v, E, dl, 2 * n, st));
+        HIP_TRY(launch_moddown_conv(c, level, true, ws.v, ws.w, 2 * n, st));
+        HIP_TRY(launch_ntt(c, false, ws.w, level, ws.w, level, range_list(0, level, 0), 2 * n, st));
+        HIP_TRY(launch_moddown_final(c, level, true, ws.v, ws.w, items, n, st));
+        return CKKS_OK;
+    }
     HIP_TRY(launch_ntt(c, true, ws.v, E, ws.v, E, range_list(L1, k, c->num_q), 2 * n, st));  // P-part -> coefficients
-    HIP_TRY(launch_moddown_conv(c, level, ws.v, ws.w, 2 * n, st));
+    HIP_TRY(launch_moddown_conv(c, level, false, ws.v, ws.w, 2 * n, st));
     HIP_TRY(launch_ntt(c, false, ws.w, L1, ws.w, L1, range_list(0, L1, 0), 2 * n, st));
-    HIP_TRY(launch_moddown_final(c, level, ws.v, ws.w, items, n, st));
+    HIP_TRY(launch_moddown_final(c, level, false, ws.v, ws.w, items, n, st));
     return CKKS_OK;
 }
 
@@ -156,7 +168,7 @@ int run_ctct(const ckks_ctx* c, u32 level, const u64* const* a, size_t a_cstride
     u64* d2 = ar.take(n * L1 * N);
     KsWs ws;
     if (!carve_ks(c, level, n, n, ar, ws)) return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for ct-ct multiply");
-    HIP_TRY(launch_tensor(c, level, ptr_list(a, n), a_cstride, ptr_list(b, n), b_cstride, d0, d1, d2, n, st));
+    HIP_TRY(launch_tensor(c, level, ptr_list(a, n), a_cstride, ptr_list(b, n), b_cstride, d0, d1, d2, n, nullptr, 0, st));
     const u64* d2s[CT_BATCH];
     FinalItem items[CT_BATCH];
     for (u32 i = 0; i < n; i++) {
@@ -167,6 +179,35 @@ int run_ctct(const ckks_ctx* c, u32 level, const u64* const* a, size_t a_cstride
     if (rc) return rc;
     HIP_TRY(launch_key_inner_multi(c, level, ws.digits, ws.dig_b, d_rlk, 1, ws.v, ws.v_b, n, st));
     return run_moddown(c, level, ws, n, items, st);
+}
+
+// n <= CT_BATCH products Rescale(a[b]*b[b] + addend[b]) with the relinearisation's ModDown and the rescale merged into
+// one division by P*q_level: the tensor product's d0, d1 (plus the addend) enter the extended basis as P times
+// themselves inside the inner-product kernel.  addend (optional): n ciphertexts [2][level+1][N], item stride
+// add_bstride.  outs[b] = [2][level][N].
+int run_ctct_merged(const ckks_ctx* c, u32 level, const u64* const* a, size_t a_cstride, const u64* const* b, size_t b_cstride,
+                    const u64* addend, size_t add_bstride, const u64* d_rlk, u64* const* outs, u32 n, Arena ar, hipStream_t st) {
+    const size_t N = c->N, L1 = level + 1;
+    u64* d0 = ar.take(n * L1 * N);
+    u64* d1 = ar.take(n * L1 * N);
+    u64* d2 = ar.take(n * L1 * N);
+    KsWs ws;
+    if (!carve_ks(c, level, n, n, ar, ws)) return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for ct-ct multiply");
+    HIP_TRY(launch_tensor(c, level, ptr_list(a, n), a_cstride, ptr_list(b, n), b_cstride, d0, d1, d2, n, addend, add_bstride, st));
+    const u64 *d2s[CT_BATCH], *add0[CT_BATCH], *add1[CT_BATCH];
+    u64* vs[CT_BATCH];
+    FinalItem items[CT_BATCH];
+    for (u32 i = 0; i < n; i++) {
+        d2s[i] = d2 + i * L1 * N;
+        add0[i] = d0 + i * L1 * N;
+        add1[i] = d1 + i * L1 * N;
+        vs[i] = ws.v + i * ws.v_b;
+        items[i] = FinalItem{nullptr, nullptr, nullptr, outs[i], 1, 0};
+    }
+    int rc = run_modup(c, level, d2s, n, ws, st);
+    if (rc) return rc;
+    HIP_TRY(launch_key_inner_ext(c, level, ws.digits, ws.dig_b, d_rlk, 1, add0, add1, nullptr, vs, n, st));
+    return run_moddown(c, level, ws, n, items, st, true);
 }
 
 size_t ws_poly_act(const ckks_ctx* c, u32 level, u32 n) {
@@ -183,6 +224,7 @@ int conv_deferred(const ckks_ctx* c, const he_conv_desc* d, const u32* gs, const
                   const ckks_key* const* rot_keys, const u64* masks, const u64* w_res, uint64_t* const* h_d_out, void* d_ws,
                   size_t ws_bytes, hipStream_t st) {
     const u32 level = d->level, E = c->ext_limbs(level);
+    const bool merged = d->alignment == HE_CONV_DEFERRED_MERGED;  // ModDown and rescale of the sums as one division
     const size_t N = c->N, L1 = level + 1, ct_elems = 2 * L1 * N, x_elems = 2 * (size_t)E * N;
     Arena ar(d_ws, ws_bytes);
     KsWs ws;
@@ -210,7 +252,7 @@ int conv_deferred(const ckks_ctx* c, const he_conv_desc* d, const u32* gs, const
                 for (u32 b = 0; b < n; b++) HIP_TRY(launch_centre_ext(c, level, mask, in[b], outs[b], st));
                 continue;
             }
-            HIP_TRY(launch_key_inner_ext(c, level, ws.digits, ws.dig_b, rot_keys[t]->d_key, gs[t], in, mask, outs, n, st));
+            HIP_TRY(launch_key_inner_ext(c, level, ws.digits, ws.dig_b, rot_keys[t]->d_key, gs[t], in, nullptr, mask, outs, n, st));
         }
     }
     HIP_TRY(launch_weighted_sum(c, level, true, xs, d->c_in * 9, w_res, d->c_out, acc, wscratch, st));
@@ -223,13 +265,13 @@ int conv_deferred(const ckks_ctx* c, const he_conv_desc* d, const u32* gs, const
         const u64* ins[CT_BATCH];
         u64* outs[CT_BATCH];
         for (u32 b = 0; b < n; b++) {
-            items[b] = FinalItem{nullptr, nullptr, nullptr, tmp + (size_t)b * ct_elems, 1, 0};
             ins[b] = tmp + (size_t)b * ct_elems;
             outs[b] = (u64*)h_d_out[o0 + b];
+            items[b] = FinalItem{nullptr, nullptr, nullptr, merged ? outs[b] : tmp + (size_t)b * ct_elems, 1, 0};
         }
-        int rc = run_moddown(c, level, wd, n, items, st);
+        int rc = run_moddown(c, level, wd, n, items, st, merged);
         if (rc) return rc;
-        if ((rc = run_rescale(c, level, ins, L1 * N, outs, n, ar.rest(), st))) return rc;
+        if (!merged && (rc = run_rescale(c, level, ins, L1 * N, outs, n, ar.rest(), st))) return rc;
     }
     return CKKS_OK;
 }
@@ -255,7 +297,7 @@ size_t ckks_workspace_bytes(const ckks_ctx* c, int op, uint32_t level, uint32_t 
 size_t he_conv_workspace_bytes(const ckks_ctx* c, const he_conv_desc* d) {
     if (!c || !d || !c->dnum || !level_ok(c, d->level) || d->level < 1) return 0;
     const size_t N = c->N, L1 = d->level + 1;
-    if (d->alignment == HE_CONV_DEFERRED_MODDOWN) {
+    if (d->alignment == HE_CONV_DEFERRED_MODDOWN || d->alignment == HE_CONV_DEFERRED_MERGED) {
         const size_t E = c->ext_limbs(d->level);
         return ws_ks(c, d->level, CT_BATCH, CT_BATCH) + blk((size_t)d->c_in * 9 * 2 * E * N) + blk((size_t)d->c_out * 2 * E * N) +
                blk(weighted_sum_scratch_elems(c, (u32)E, d->c_in * 9, d->c_out)) + blk((size_t)CT_BATCH * 2 * L1 * N) +
@@ -462,8 +504,7 @@ int he_conv_batched(const ckks_ctx* c, const he_conv_desc* d, const uint64_t* co
         return set_err(c, CKKS_ERR_INVALID_ARG, "empty convolution shape");
     if (!level_ok(c, d->level) || d->level < 1) return set_err(c, CKKS_ERR_LEVEL_MISMATCH, "convolution needs 1 <= level < num_q");
     if ((u64)d->height * d->width * d->batch > c->N / 2) return set_err(c, CKKS_ERR_INVALID_ARG, "H*W*batch exceeds the N/2 slots");
-    if (d->alignment != HE_CONV_ALIGN_DIRECT && d->alignment != HE_CONV_ALIGN_FOUR_KEYS && d->alignment != HE_CONV_DEFERRED_MODDOWN)
-        return set_err(c, CKKS_ERR_INVALID_ARG, "unknown alignment");
+    if (d->alignment > HE_CONV_DEFERRED_MERGED) return set_err(c, CKKS_ERR_INVALID_ARG, "unknown alignment");
     const bool four = d->alignment == HE_CONV_ALIGN_FOUR_KEYS;
     const u32 level = d->level;
     const size_t N = c->N, L1 = level + 1, ct_elems = 2 * L1 * N;
@@ -482,7 +523,7 @@ int he_conv_batched(const ckks_ctx* c, const he_conv_desc* d, const uint64_t* co
     for (u32 i = 0; i < d->c_in; i++) if (!h_d_in[i]) return set_err(c, CKKS_ERR_INVALID_ARG, "null input ciphertext");
     for (u32 o = 0; o < d->c_out; o++) if (!h_d_out[o]) return set_err(c, CKKS_ERR_INVALID_ARG, "null output ciphertext");
 
-    if (d->alignment == HE_CONV_DEFERRED_MODDOWN)
+    if (d->alignment == HE_CONV_DEFERRED_MODDOWN || d->alignment == HE_CONV_DEFERRED_MERGED)
         return conv_deferred(c, d, gs, h_d_in, rot_keys, (const u64*)d_tap_masks, (const u64*)d_w_res, h_d_out, d_ws, ws_bytes,
                              (hipStream_t)stream);
     Arena ar(d_ws, ws_bytes);
@@ -647,7 +688,7 @@ int he_accumulator_merge(const ckks_ctx* c, const uint64_t* const* h_d_cts, uint
 }
 
 int he_poly_act_deg7(const ckks_ctx* c, const uint64_t* const* h_d_x, uint32_t n_ct, uint32_t level, const int64_t* h_k,
-                     const ckks_key* rlk, uint64_t* const* h_d_out, void* d_ws, size_t ws_bytes, void* stream) {
+                     const ckks_key* rlk, int merged_division, uint64_t* const* h_d_out, void* d_ws, size_t ws_bytes, void* stream) {
     if (!c) return CKKS_ERR_INVALID_ARG;
     if (!h_d_x || !h_k || !h_d_out || n_ct == 0) return set_err(c, CKKS_ERR_INVALID_ARG, "null pointer or no ciphertexts");
     if (!c->dnum) return set_err(c, CKKS_ERR_UNSUPPORTED_PARAMS, "context has no key-switching digits");
@@ -695,6 +736,22 @@ int he_poly_act_deg7(const ckks_ctx* c, const uint64_t* const* h_d_x, uint32_t n
             for (u32 b = 0; b < n; b++) ptmp[b] = otmp[b] = tmp + b * 2 * cstride;
         };
         int rc;
+        if (merged_division) {  // every relinearise-then-rescale pair as one division by P*q_level
+            if ((rc = run_ctct_merged(c, level, px, xs, px, xs, nullptr, 0, rlk->d_key, ox2, n, ar.rest(), st))) return rc;
+            if ((rc = run_ctct_merged(c, l1, px2, x2s, px, xs, nullptr, 0, rlk->d_key, ox3, n, ar.rest(), st))) return rc;
+            if ((rc = run_ctct_merged(c, l1, px2, x2s, px2, x2s, nullptr, 0, rlk->d_key, ox4, n, ar.rest(), st))) return rc;
+            residues(h_k[2], l2, ka);
+            residues(h_k[3], l2, kb);
+            tmp_at(x3s);
+            HIP_TRY(launch_lincomb2(c, l2, ptr_list(px, n), xs, ka, ptr_list(px3, n), x3s, kb, nullptr, 0, tmp, 2 * x3s, n, st));
+            if ((rc = run_rescale(c, l2, ptmp, x3s, oB, n, ar.rest(), st))) return rc;
+            // y = Rescale(x4 * B + (k1 * x + k3 * x3)): the linear part rides along as the product's addend
+            residues(h_k[0], l3, ka);
+            residues(h_k[1], l3, kb);
+            HIP_TRY(launch_lincomb2(c, l3, ptr_list(px, n), xs, ka, ptr_list(px3, n), x3s, kb, nullptr, 0, tmp, 2 * Bs, n, st));
+            if ((rc = run_ctct_merged(c, l3, px4, x3s, pB, Bs, tmp, 2 * Bs, rlk->d_key, oout, n, ar.rest(), st))) return rc;
+            continue;
+        }
         // x2 = Rescale(x * x)                                  level -> level-1
         tmp_at(xs);
         if ((rc = run_ctct(c, level, px, xs, px, xs, rlk->d_key, otmp, n, ar.rest(), st))) return rc;

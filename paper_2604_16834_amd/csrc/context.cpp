@@ -67,6 +67,7 @@ extern "C" void ckks_ctx_destroy(ckks_ctx* c) {
     (void)hipFree(c->d_mcf);
     (void)hipFree(c->d_modup);
     (void)hipFree(c->d_moddown);
+    (void)hipFree(c->d_moddown_rs);
     (void)hipFree(c->d_rescale);
     delete c;
 }
@@ -82,7 +83,7 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
     if (p->dnum != 0 && (p->dnum > p->num_q || p->num_p < 1)) return fail(CKKS_ERR_INVALID_ARG, "need 1 <= dnum <= num_q and num_p >= 1");
     const u32 N = 1u << p->log_n;
     const u32 alpha = p->dnum ? (p->num_q + p->dnum - 1) / p->dnum : 0;
-    if (alpha > 16 || p->num_p > 16) return fail(CKKS_ERR_UNSUPPORTED_PARAMS, "at most 16 limbs per digit and 16 special primes");
+    if (alpha > 16 || p->num_p > 15) return fail(CKKS_ERR_UNSUPPORTED_PARAMS, "at most 16 limbs per digit and 15 special primes");
     u32 bmin = 64, bmax = 0;
     for (u32 t = 0; t < M; t++) {
         const u64 q = p->moduli[t];
@@ -111,6 +112,7 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
     auto pad = [](u32 v) { return v <= 4 ? 4u : (v <= 8 ? 8u : 16u); };
     c->alpha_pad = pad(alpha);
     c->k_pad = pad(p->num_p);
+    c->k2_pad = p->num_p + 1 > 8 && p->num_p + 1 <= 12 ? 12u : pad(p->num_p + 1);  // 9..12 dropped limbs: rows of 12
     c->mod.assign(p->moduli, p->moduli + M);
     c->psi.assign(p->psi, p->psi + M);
 
@@ -215,6 +217,40 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
             moddown[2 * kp + (size_t)kp * nq + 2 * nq + i] = (qi - P) % qi;  // -P mod q_i
         }
     }
+    // the same constants for the dropped set D(l) = {q_l, p_0..p_{k-1}} of every level l >= 1
+    std::vector<u64> moddown_rs;
+    if (c->dnum) {
+        const u32 k = c->num_p, nq = c->num_q, kp = c->k2_pad;
+        moddown_rs.assign((size_t)nq * c->moddown_rs_stride(), 0);
+        for (u32 l = 1; l < nq; l++) {
+            u64* tab = moddown_rs.data() + l * c->moddown_rs_stride();
+            std::vector<u64> drop(1, c->mod[l]);
+            for (u32 b = 0; b < k; b++) drop.push_back(c->mod[nq + b]);
+            for (u32 a = 0; a <= k; a++) {
+                const u64 da = drop[a];
+                u64 dhat = 1;
+                for (u32 b = 0; b <= k; b++) if (b != a) dhat = h_mulmod(dhat, drop[b] % da, da);
+                const u64 inv = h_invmod(dhat, da);
+                tab[a] = inv;
+                tab[kp + a] = h_shoup(inv, da);
+                for (u32 i = 0; i < l; i++) {
+                    const u64 qi = c->mod[i];
+                    u64 v = 1;
+                    for (u32 b = 0; b <= k; b++) if (b != a) v = h_mulmod(v, drop[b] % qi, qi);
+                    tab[2 * kp + (size_t)i * kp + a] = v;
+                }
+            }
+            for (u32 i = 0; i < l; i++) {
+                const u64 qi = c->mod[i];
+                u64 D = 1;
+                for (u32 b = 0; b <= k; b++) D = h_mulmod(D, drop[b] % qi, qi);
+                const u64 dinv = h_invmod(D, qi);
+                tab[2 * kp + (size_t)kp * nq + i] = dinv;
+                tab[2 * kp + (size_t)kp * nq + nq + i] = h_shoup(dinv, qi);
+                tab[2 * kp + (size_t)kp * nq + 2 * nq + i] = (qi - D) % qi;
+            }
+        }
+    }
     // rescale table [l][i] = (q_l^-1 mod q_i, Shoup companion, q_l mod q_i)
     std::vector<u64> resc((size_t)c->num_q * c->num_q * 3, 0);
     for (u32 l = 0; l < c->num_q; l++)
@@ -234,6 +270,7 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
     if (e == hipSuccess) e = upload(mcf, &c->d_mcf);
     if (e == hipSuccess) e = upload(modup, &c->d_modup);
     if (e == hipSuccess) e = upload(moddown, &c->d_moddown);
+    if (e == hipSuccess) e = upload(moddown_rs, &c->d_moddown_rs);
     if (e == hipSuccess) e = upload(resc, &c->d_rescale);
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {

@@ -97,6 +97,8 @@ struct ckks_ctx {
     ModConstF* d_mcf = nullptr;       // [M]
     u64* d_modup = nullptr;           // per level, per digit: see modup_digit_stride()
     u64* d_moddown = nullptr;         // phat_inv[k_pad], phat_inv_sh[k_pad], phat_q[num_q][k_pad], pinv[num_q], pinv_sh[num_q], negp[num_q]
+    u64* d_moddown_rs = nullptr;      // per level l >= 1, the same layout (k_pad -> k2_pad) for the dropped set {q_l, p_0..p_{k-1}}:
+                                      // ModDown and rescale as one division by P*q_l; see moddown_rs_table()
     u64* d_rescale = nullptr;         // [num_q][num_q][3]: (q_l^-1 mod q_i, its Shoup companion, q_l mod q_i)
 
     mutable std::string err;
@@ -111,7 +113,10 @@ struct ckks_ctx {
     // indexed by the position e in the extended basis of that level; negq = -Q_j mod t).  The alpha
     // constants of one target limb are adjacent so that a wavefront fetches them with one wide scalar load.
     // Rows are padded to alpha_pad / k_pad entries (4, 8 or 16; zeros beyond the real ones).
-    u32 alpha_pad, k_pad;
+    u32 alpha_pad, k_pad, k2_pad;  // k2_pad: padded num_p + 1
+    // rounded up to 16 words so that every level's rows keep the 128-byte alignment the wide scalar loads assume
+    size_t moddown_rs_stride() const { return (2 * (size_t)k2_pad + (size_t)k2_pad * num_q + 3 * num_q + 15) / 16 * 16; }
+    const u64* moddown_rs_table(u32 level) const { return d_moddown_rs + level * moddown_rs_stride(); }
     size_t modup_negq_off() const { return (size_t)alpha_pad * (2 + M); }
     size_t modup_digit_stride() const { return modup_negq_off() + ((M + 15) / 16) * 16; }
     size_t modup_level_stride() const { return modup_digit_stride() * dnum; }
@@ -150,10 +155,14 @@ hipError_t launch_modup_conv(const ckks_ctx* c, u32 level, u32 j, const u64* y, 
 hipError_t launch_key_inner(const ckks_ctx* c, u32 level, const u64* digits, const u64* key, u32 g, u64* v, hipStream_t st);
 hipError_t launch_key_inner_multi(const ckks_ctx* c, u32 level, const u64* digits, size_t digits_bstride, const u64* key, u32 g,
                                   u64* v, size_t v_bstride, u32 n, hipStream_t st);
+// add0s / add1s: per item, polynomials [level+1][N] whose P-fold is added to component 0 / 1 (either list, or entries, may be null)
 hipError_t launch_key_inner_ext(const ckks_ctx* c, u32 level, const u64* digits, size_t digits_bstride, const u64* key, u32 g,
-                                const u64* const* c0s, const u64* mask, u64* const* outs, u32 n, hipStream_t st);
-hipError_t launch_moddown_conv(const ckks_ctx* c, u32 level, const u64* v, u64* w, u32 batch, hipStream_t st);
-hipError_t launch_moddown_final(const ckks_ctx* c, u32 level, const u64* v, const u64* w, const FinalItem* items, u32 n, hipStream_t st);
+                                const u64* const* add0s, const u64* const* add1s, const u64* mask, u64* const* outs, u32 n,
+                                hipStream_t st);
+// merged: the dropped limbs are q_level and the special primes (division by P*q_level, results on limbs 0..level-1)
+hipError_t launch_moddown_conv(const ckks_ctx* c, u32 level, bool merged, const u64* v, u64* w, u32 batch, hipStream_t st);
+hipError_t launch_moddown_final(const ckks_ctx* c, u32 level, bool merged, const u64* v, const u64* w, const FinalItem* items, u32 n,
+                                hipStream_t st);
 // pointwise.hip
 hipError_t launch_automorph(const ckks_ctx* c, u32 n_polys, const u64* in, u32 g, u64* out, hipStream_t st);
 hipError_t launch_copy(const u64* in, u64* out, size_t n, hipStream_t st);
@@ -163,7 +172,7 @@ hipError_t launch_rescale_conv(const ckks_ctx* c, u32 level, const u64* r, u64* 
 hipError_t launch_rescale_final(const ckks_ctx* c, u32 level, const PtrList8& ct, size_t ct_cstride, const u64* w, const OutList8& out,
                                 u32 n, hipStream_t st);
 hipError_t launch_tensor(const ckks_ctx* c, u32 level, const PtrList8& a, size_t a_cstride, const PtrList8& b, size_t b_cstride,
-                         u64* d0, u64* d1, u64* d2, u32 n, hipStream_t st);
+                         u64* d0, u64* d1, u64* d2, u32 n, const u64* add, size_t add_bstride, hipStream_t st);
 hipError_t launch_mask_mul(const ckks_ctx* c, u32 level, const u64* mask, const u64* ct, u64* out, hipStream_t st);
 hipError_t launch_ct_sum(const ckks_ctx* c, u32 level, const PtrList8& items, u32 n, u64* out, hipStream_t st);
 hipError_t launch_centre_ext(const ckks_ctx* c, u32 level, const u64* mask, const u64* ct, u64* out, hipStream_t st);

@@ -231,13 +231,16 @@ hipError_t launch_key_inner_multi(const ckks_ctx* c, u32 level, const u64* digit
     return hipGetLastError();
 }
 
-// The inner product of a batch, finished for a convolution that divides by P once, after its sum
-// over (input channel, tap): the aligned copy of ciphertext b before its ModDown, times the tap's mask,
-//   out_b[comp][e][x] = mask[e][x] * ( v_b[comp][e][x] + (comp == 0 && e <= level ? [P]_{q_e} * c0_b[e][sigma_g x] : 0) )
-// on all E limbs of the extended basis (mask [E][N] on that basis too); P * sigma_g(c0) vanishes on the
-// special primes.  P * c0 joins the unreduced 128-bit sum as one more term.
+// The inner product of a batch, finished for an operation that divides by P later (the convolution that
+// takes one ModDown per output channel after its sum; the ciphertext product whose ModDown is merged with
+// the rescale): on all E limbs of the extended basis,
+//   out_b[comp][e][x] = mask[e][x] * ( v_b[comp][e][x] + (e <= level ? [P]_{q_e} * add_comp,b[e][sigma_g x] : 0) )
+// add0 / add1 [level+1][N] (optional) are what the result of the key switch would have been added to
+// (Rot: c0; relinearisation: d0, d1); P times them vanishes on the special primes and joins the
+// unreduced 128-bit sum as one more term.  mask [E][N] (optional): a plaintext on the extended basis.
 struct ExtItems {
-    const u64* c0[KS_MAX_BATCH];
+    const u64* add0[KS_MAX_BATCH];
+    const u64* add1[KS_MAX_BATCH];
     u64* out[KS_MAX_BATCH];
 };
 
@@ -253,63 +256,70 @@ __global__ __launch_bounds__(KS_THREADS) void key_inner_ext_kernel(const u64* __
     const u32 t = e <= level ? e : num_q + (e - level - 1);
     const u32 xs = g == 1 ? x : galois_gather_index(x, g, log_n);
     const ModConst m = mc[t];
-    const u64 mk = mask[(size_t)e * N + x];
-    const bool has_c0 = e <= level;
-    const u64 pres = has_c0 ? m.q - negp[e] : 0;  // P mod q_e
+    const bool has_mask = mask != nullptr;
+    const u64 mk = has_mask ? mask[(size_t)e * N + x] : 0;
+    const bool has_add = e <= level;
+    const u64 pres = has_add ? m.q - negp[e] : 0;  // P mod q_e
+    u64 k0[4], k1[4];  // beta <= 4: the thread's key words stay in registers for the whole batch
     if (beta <= 4) {
-        u64 k0[4], k1[4];
 #pragma unroll
         for (u32 j = 0; j < 4; j++) {
             k0[j] = j < beta ? key[(((size_t)j * 2 + 0) * M + t) * N + x] : 0;
             k1[j] = j < beta ? key[(((size_t)j * 2 + 1) * M + t) * N + x] : 0;
         }
-        for (u32 b = 0; b < n; b++) {
-            const u64* d = digits + b * digits_bstride;
-            U128 acc0 = {0, 0}, acc1 = {0, 0};
+    }
+    for (u32 b = 0; b < n; b++) {
+        const u64* d = digits + b * digits_bstride;
+        U128 acc0 = {0, 0}, acc1 = {0, 0};
+        if (beta <= 4) {
 #pragma unroll
             for (u32 j = 0; j < 4; j++) {
                 const u64 dv = j < beta ? d[((size_t)j * E + e) * N + xs] : 0;
                 acc_wide(acc0, dv, k0[j]);
                 acc_wide(acc1, dv, k1[j]);
             }
-            if (has_c0) acc_wide(acc0, items.c0[b][(size_t)e * N + xs], pres);
-            u64* ob = items.out[b];
-            ob[((size_t)0 * E + e) * N + x] = mulmod_barrett(barrett_reduce(acc0, m), mk, m);
-            ob[((size_t)1 * E + e) * N + x] = mulmod_barrett(barrett_reduce(acc1, m), mk, m);
-        }
-        return;
-    }
-    for (u32 b = 0; b < n; b++) {
-        const u64* d = digits + b * digits_bstride;
-        U128 acc0 = {0, 0}, acc1 = {0, 0};
-        for (u32 j = 0; j < beta; j++) {
-            const u64 dv = d[((size_t)j * E + e) * N + xs];
-            acc_wide(acc0, dv, key[(((size_t)j * 2 + 0) * M + t) * N + x]);
-            acc_wide(acc1, dv, key[(((size_t)j * 2 + 1) * M + t) * N + x]);
-            if ((j & 15) == 15) {
-                acc0.lo = barrett_reduce(acc0, m); acc0.hi = 0;
-                acc1.lo = barrett_reduce(acc1, m); acc1.hi = 0;
+        } else {
+            for (u32 j = 0; j < beta; j++) {
+                const u64 dv = d[((size_t)j * E + e) * N + xs];
+                acc_wide(acc0, dv, key[(((size_t)j * 2 + 0) * M + t) * N + x]);
+                acc_wide(acc1, dv, key[(((size_t)j * 2 + 1) * M + t) * N + x]);
+                if ((j & 15) == 15) {
+                    acc0.lo = barrett_reduce(acc0, m); acc0.hi = 0;
+                    acc1.lo = barrett_reduce(acc1, m); acc1.hi = 0;
+                }
             }
         }
-        if (has_c0) acc_wide(acc0, items.c0[b][(size_t)e * N + xs], pres);
+        if (has_add && items.add0[b]) acc_wide(acc0, items.add0[b][(size_t)e * N + xs], pres);
+        if (has_add && items.add1[b]) acc_wide(acc1, items.add1[b][(size_t)e * N + xs], pres);
+        u64 r0 = barrett_reduce(acc0, m), r1 = barrett_reduce(acc1, m);
+        if (has_mask) {
+            r0 = mulmod_barrett(r0, mk, m);
+            r1 = mulmod_barrett(r1, mk, m);
+        }
         u64* ob = items.out[b];
-        ob[((size_t)0 * E + e) * N + x] = mulmod_barrett(barrett_reduce(acc0, m), mk, m);
-        ob[((size_t)1 * E + e) * N + x] = mulmod_barrett(barrett_reduce(acc1, m), mk, m);
+        ob[((size_t)0 * E + e) * N + x] = r0;
+        ob[((size_t)1 * E + e) * N + x] = r1;
     }
 }
 
-// c0s / outs: host arrays of n <= KS_MAX_BATCH device pointers ([level+1][N] and [2][E][N])
+// add0s / add1s / outs: host arrays of n <= KS_MAX_BATCH device pointers ([level+1][N], [level+1][N], [2][E][N]);
+// add0s, add1s or single entries of them may be null
 hipError_t launch_key_inner_ext(const ckks_ctx* c, u32 level, const u64* digits, size_t digits_bstride, const u64* key, u32 g,
-                                const u64* const* c0s, const u64* mask, u64* const* outs, u32 n, hipStream_t st) {
+                                const u64* const* add0s, const u64* const* add1s, const u64* mask, u64* const* outs, u32 n,
+                                hipStream_t st) {
     const u32 E = c->ext_limbs(level), beta = c->live_digits(level);
     ExtItems items;
+    double n_add = 0.0;
     for (u32 b = 0; b < KS_MAX_BATCH; b++) {
-        items.c0[b] = b < n ? c0s[b] : nullptr;
+        items.add0[b] = (b < n && add0s) ? add0s[b] : nullptr;
+        items.add1[b] = (b < n && add1s) ? add1s[b] : nullptr;
         items.out[b] = b < n ? outs[b] : nullptr;
+        n_add += (items.add0[b] ? 1.0 : 0.0) + (items.add1[b] ? 1.0 : 0.0);
     }
     const u64* negp = c->d_moddown + 2 * c->k_pad + (size_t)c->k_pad * c->num_q + 2 * c->num_q;
     dim3 grid((c->N + KS_THREADS - 1) / KS_THREADS, E);
-    ProfScope ps__(c, K_KEY_INNER, st, 8.0 * c->N * (E * (2.0 * beta + 1.0 + n * (beta + 2.0)) + n * (level + 1.0)), 2.0 * n * c->N * E * (beta + 1.0));
+    ProfScope ps__(c, K_KEY_INNER, st, 8.0 * c->N * (E * (2.0 * beta + (mask ? 1.0 : 0.0) + n * (beta + 2.0)) + n_add * (level + 1.0)),
+                   2.0 * n * c->N * E * (beta + 1.0));
     hipLaunchKernelGGL(key_inner_ext_kernel, grid, dim3(KS_THREADS), 0, st, digits, digits_bstride, key, items, mask, negp, c->d_mc,
                        c->log_n, level, c->num_q, c->M, E, beta, g, n);
     return hipGetLastError();
@@ -318,9 +328,16 @@ hipError_t launch_key_inner_ext(const ckks_ctx* c, u32 level, const u64* digits,
 // ---- ModDown, conversion of the P-part ----------------------------------------------------------
 // v [2][E][N]: limbs level+1.. hold the P-part in coefficient form.  w [2][level+1][N] (coefficients)
 #define MODDOWN_LIMBS_PER_BLOCK 12
+// Dropped limbs: positions first..first+k-1 of v's E limbs; their moduli: `merged` ? (q_level, p_0, ...) : (p_0, ...).
+// Results on limbs 0..n_out-1 (n_out = level+1, or level when merged).
+__device__ __forceinline__ u32 dropped_modulus(u32 a, u32 level, u32 num_q, bool merged) {
+    return merged ? (a == 0 ? level : num_q + a - 1) : num_q + a;
+}
+
 __global__ __launch_bounds__(KS_THREADS) void moddown_conv_kernel(const u64* __restrict__ v, u64* __restrict__ w,
                                                                   const u64* __restrict__ tab, const ModConst* __restrict__ mc,
-                                                                  u32 N, u32 level, u32 num_q, u32 k, u32 kp, u32 E) {
+                                                                  u32 N, u32 level, u32 num_q, u32 k, u32 kp, u32 E, u32 first,
+                                                                  u32 n_out, bool merged) {
     const u32 x = blockIdx.x * KS_THREADS + threadIdx.x;
     if (x >= N) return;
     const u32 comp = blockIdx.z;
@@ -329,27 +346,28 @@ __global__ __launch_bounds__(KS_THREADS) void moddown_conv_kernel(const u64* __r
 #pragma unroll
     for (u32 a = 0; a < KS_MAX_DIGIT; a++)
         if (a < k) {
-            const u64 pa = mc[num_q + a].q;
-            z[a] = mul_shoup(v[((size_t)comp * E + level + 1 + a) * N + x], tab[a], tab[kp + a], pa);
+            const u64 pa = mc[dropped_modulus(a, level, num_q, merged)].q;
+            z[a] = mul_shoup(v[((size_t)comp * E + first + a) * N + x], tab[a], tab[kp + a], pa);
             n_neg += z[a] > (pa >> 1) ? 1 : 0;
         }
     const u64* phat_q = tab + 2 * kp;  // [num_q][kp]
     const u64* negp = tab + 2 * kp + (size_t)kp * num_q + 2 * num_q;
     const u32 i0 = blockIdx.y * MODDOWN_LIMBS_PER_BLOCK;
-    for (u32 i = i0; i < i0 + MODDOWN_LIMBS_PER_BLOCK && i <= level; i++) {
+    for (u32 i = i0; i < i0 + MODDOWN_LIMBS_PER_BLOCK && i < n_out; i++) {
         U128 acc = {0, 0};
 #pragma unroll
         for (u32 a = 0; a < KS_MAX_DIGIT; a++)
             if (a < k) acc_wide(acc, z[a], phat_q[(size_t)i * kp + a]);
         acc_wide(acc, n_neg, negp[i]);
-        w[((size_t)comp * (level + 1) + i) * N + x] = barrett_reduce(acc, mc[i]);
+        w[((size_t)comp * n_out + i) * N + x] = barrett_reduce(acc, mc[i]);
     }
 }
 
 template <int KP>
 __global__ __launch_bounds__(KS_THREADS) void moddown_conv50_kernel(const u64* __restrict__ v, u64* __restrict__ w,
                                                                     const u64* __restrict__ tab, const ModConst* __restrict__ mc,
-                                                                    u32 N, u32 level, u32 num_q, u32 k, u32 E) {
+                                                                    u32 N, u32 level, u32 num_q, u32 k, u32 E, u32 first, u32 n_out,
+                                                                    bool merged) {
     const u32 x = blockIdx.x * KS_THREADS + threadIdx.x;
     if (x >= N) return;
     const u32 comp = blockIdx.z;
@@ -359,17 +377,18 @@ __global__ __launch_bounds__(KS_THREADS) void moddown_conv50_kernel(const u64* _
     for (u32 a = 0; a < KP; a++) {
         z[a] = {0, 0, 0};
         if (a < k) {
-            const u64 pa = mc[num_q + a].q;
-            const u64 zv = mul_shoup(v[((size_t)comp * E + level + 1 + a) * N + x], tab[a], tab[KP + a], pa);
+            const u64 pa = mc[dropped_modulus(a, level, num_q, merged)].q;
+            const u64 zv = mul_shoup(v[((size_t)comp * E + first + a) * N + x], tab[a], tab[KP + a], pa);
             n_neg += zv > (pa >> 1) ? 1 : 0;
             z[a] = split50(zv);
         }
     }
-    const u64* phat_q = (const u64*)__builtin_assume_aligned(tab + 2 * KP, 8 * KP);  // [num_q][KP]
+    constexpr int ROW_ALIGN = (KP & (KP - 1)) == 0 ? 8 * KP : 32;  // rows of 12 words are 32-byte aligned
+    const u64* phat_q = (const u64*)__builtin_assume_aligned(tab + 2 * KP, ROW_ALIGN);  // [num_q][KP]
     const u64* negp = tab + 2 * KP + (size_t)KP * num_q + 2 * num_q;
     const u32 i0 = blockIdx.y * MODDOWN_LIMBS_PER_BLOCK;
-    for (u32 i = i0; i < i0 + MODDOWN_LIMBS_PER_BLOCK && i <= level; i++) {
-        const u64* pe = (const u64*)__builtin_assume_aligned(phat_q + (size_t)i * KP, 8 * KP);
+    for (u32 i = i0; i < i0 + MODDOWN_LIMBS_PER_BLOCK && i < n_out; i++) {
+        const u64* pe = (const u64*)__builtin_assume_aligned(phat_q + (size_t)i * KP, ROW_ALIGN);
         u64 cv[KP];
 #pragma unroll
         for (u32 a = 0; a < KP; a++) cv[a] = pe[a];
@@ -378,24 +397,28 @@ __global__ __launch_bounds__(KS_THREADS) void moddown_conv50_kernel(const u64* _
         for (u32 a = 0; a < KP; a++) acc50_mad(acc, z[a], split50(cv[a]));
         U128 s = acc50_value(acc);
         acc_wide(s, n_neg, negp[i]);
-        w[((size_t)comp * (level + 1) + i) * N + x] = barrett_reduce(s, mc[i]);
+        w[((size_t)comp * n_out + i) * N + x] = barrett_reduce(s, mc[i]);
     }
 }
 
-hipError_t launch_moddown_conv(const ckks_ctx* c, u32 level, const u64* v, u64* w, u32 batch, hipStream_t st) {
-    dim3 grid((c->N + KS_THREADS - 1) / KS_THREADS, (level + 1 + MODDOWN_LIMBS_PER_BLOCK - 1) / MODDOWN_LIMBS_PER_BLOCK, batch);
+hipError_t launch_moddown_conv(const ckks_ctx* c, u32 level, bool merged, const u64* v, u64* w, u32 batch, hipStream_t st) {
+    const u32 n_out = merged ? level : level + 1, k = merged ? c->num_p + 1 : c->num_p, kp = merged ? c->k2_pad : c->k_pad;
+    const u32 first = merged ? level : level + 1, E = c->ext_limbs(level);
+    const u64* tab = merged ? c->moddown_rs_table(level) : c->d_moddown;
+    dim3 grid((c->N + KS_THREADS - 1) / KS_THREADS, (n_out + MODDOWN_LIMBS_PER_BLOCK - 1) / MODDOWN_LIMBS_PER_BLOCK, batch);
+    ProfScope ps__(c, K_MODDOWN_CONV, st, 8.0 * batch * c->N * (k + n_out), 1.0 * batch * c->N * k * (n_out + 1.0));
     if (c->small_q) {
-        ProfScope ps__(c, K_MODDOWN_CONV, st, 8.0 * batch * c->N * (c->num_p + level + 1.0), 1.0 * batch * c->N * c->num_p * (level + 2.0));
-        if (c->k_pad == 4)
-            hipLaunchKernelGGL(moddown_conv50_kernel<4>, grid, dim3(KS_THREADS), 0, st, v, w, c->d_moddown, c->d_mc, c->N, level, c->num_q, c->num_p, c->ext_limbs(level));
-        else if (c->k_pad == 8)
-            hipLaunchKernelGGL(moddown_conv50_kernel<8>, grid, dim3(KS_THREADS), 0, st, v, w, c->d_moddown, c->d_mc, c->N, level, c->num_q, c->num_p, c->ext_limbs(level));
+        if (kp == 4)
+            hipLaunchKernelGGL(moddown_conv50_kernel<4>, grid, dim3(KS_THREADS), 0, st, v, w, tab, c->d_mc, c->N, level, c->num_q, k, E, first, n_out, merged);
+        else if (kp == 8)
+            hipLaunchKernelGGL(moddown_conv50_kernel<8>, grid, dim3(KS_THREADS), 0, st, v, w, tab, c->d_mc, c->N, level, c->num_q, k, E, first, n_out, merged);
+        else if (kp == 12)
+            hipLaunchKernelGGL(moddown_conv50_kernel<12>, grid, dim3(KS_THREADS), 0, st, v, w, tab, c->d_mc, c->N, level, c->num_q, k, E, first, n_out, merged);
         else
-            hipLaunchKernelGGL(moddown_conv50_kernel<16>, grid, dim3(KS_THREADS), 0, st, v, w, c->d_moddown, c->d_mc, c->N, level, c->num_q, c->num_p, c->ext_limbs(level));
+            hipLaunchKernelGGL(moddown_conv50_kernel<16>, grid, dim3(KS_THREADS), 0, st, v, w, tab, c->d_mc, c->N, level, c->num_q, k, E, first, n_out, merged);
         return hipGetLastError();
     }
-    { ProfScope ps__(c, K_MODDOWN_CONV, st, 8.0 * batch * c->N * (c->num_p + level + 1.0), 1.0 * batch * c->N * c->num_p * (level + 2.0)); hipLaunchKernelGGL(moddown_conv_kernel, grid, dim3(KS_THREADS), 0, st, v, w, c->d_moddown, c->d_mc, c->N, level,
-                       c->num_q, c->num_p, c->k_pad, c->ext_limbs(level)); }
+    hipLaunchKernelGGL(moddown_conv_kernel, grid, dim3(KS_THREADS), 0, st, v, w, tab, c->d_mc, c->N, level, c->num_q, k, kp, E, first, n_out, merged);
     return hipGetLastError();
 }
 
@@ -406,7 +429,7 @@ hipError_t launch_moddown_conv(const ckks_ctx* c, u32 level, const u64* v, u64* 
 // [level+1][N] multiplied into both components (the tap's validity mask of the convolution).
 __global__ __launch_bounds__(KS_THREADS) void moddown_final_kernel(const u64* __restrict__ v, const u64* __restrict__ w,
                                                                    FinalBatch B, const u64* __restrict__ tab,
-                                                                   const ModConst* __restrict__ mc, u32 log_n, u32 level,
+                                                                   const ModConst* __restrict__ mc, u32 log_n, u32 n_out,
                                                                    u32 num_q, u32 kp, u32 E) {
     const u32 N = 1u << log_n;
     const u32 x = blockIdx.x * KS_THREADS + threadIdx.x;
@@ -415,7 +438,7 @@ __global__ __launch_bounds__(KS_THREADS) void moddown_final_kernel(const u64* __
     const FinalItem it = B.it[b >> 1];
     const ModConst m = mc[i];
     const u64* pinv = tab + 2 * kp + (size_t)kp * num_q;
-    u64 d = sub_mod(v[((size_t)b * E + i) * N + x], w[((size_t)b * (level + 1) + i) * N + x], m.q);
+    u64 d = sub_mod(v[((size_t)b * E + i) * N + x], w[((size_t)b * n_out + i) * N + x], m.q);
     u64 r = mul_shoup(d, pinv[i], pinv[num_q + i], m.q);
     const u64* add = comp == 0 ? it.add0 : it.add1;
     if (add) {
@@ -423,10 +446,12 @@ __global__ __launch_bounds__(KS_THREADS) void moddown_final_kernel(const u64* __
         r = add_mod(r, add[(size_t)i * N + xs], m.q);
     }
     if (it.mask) r = mulmod_barrett(r, it.mask[(size_t)i * N + x], m);
-    it.out[((size_t)comp * (level + 1) + i) * N + x] = r;
+    it.out[((size_t)comp * n_out + i) * N + x] = r;
 }
 
-hipError_t launch_moddown_final(const ckks_ctx* c, u32 level, const u64* v, const u64* w, const FinalItem* items, u32 n, hipStream_t st) {
+// merged: division by P*q_level (results on limbs 0..level-1; addends and masks, if any, are [level][N])
+hipError_t launch_moddown_final(const ckks_ctx* c, u32 level, bool merged, const u64* v, const u64* w, const FinalItem* items, u32 n,
+                                hipStream_t st) {
     FinalBatch B;
     double extra = 0.0;
     for (u32 r = 0; r < KS_MAX_BATCH; r++) {
@@ -437,9 +462,10 @@ hipError_t launch_moddown_final(const ckks_ctx* c, u32 level, const u64* v, cons
             B.it[r] = FinalItem{nullptr, nullptr, nullptr, nullptr, 1, 0};
         }
     }
-    dim3 grid((c->N + KS_THREADS - 1) / KS_THREADS, level + 1, 2 * n);
-    ProfScope ps__(c, K_MODDOWN_FINAL, st, 8.0 * c->N * (level + 1.0) * (6.0 * n + extra), 2.0 * c->N * (level + 1.0) * n);
-    hipLaunchKernelGGL(moddown_final_kernel, grid, dim3(KS_THREADS), 0, st, v, w, B, c->d_moddown, c->d_mc, c->log_n, level,
-                       c->num_q, c->k_pad, c->ext_limbs(level));
+    const u32 n_out = merged ? level : level + 1;
+    dim3 grid((c->N + KS_THREADS - 1) / KS_THREADS, n_out, 2 * n);
+    ProfScope ps__(c, K_MODDOWN_FINAL, st, 8.0 * c->N * n_out * (6.0 * n + extra), 2.0 * c->N * n_out * n);
+    hipLaunchKernelGGL(moddown_final_kernel, grid, dim3(KS_THREADS), 0, st, v, w, B, merged ? c->moddown_rs_table(level) : c->d_moddown,
+                       c->d_mc, c->log_n, n_out, c->num_q, merged ? c->k2_pad : c->k_pad, c->ext_limbs(level));
     return hipGetLastError();
 }

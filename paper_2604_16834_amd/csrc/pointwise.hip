@@ -124,10 +124,12 @@ hipError_t launch_rescale_final(const ckks_ctx* c, u32 level, const PtrList8& ct
 }
 
 // ---- tensor product of ciphertext pairs -----------------------------------------------------------
-// item b: d0 = a0 b0, d1 = a0 b1 + a1 b0, d2 = a1 b1 on limbs 0..level; operands a.p[b], b.p[b] may sit
-// at a higher level (component strides in elements); d0/d1/d2 are [n][level+1][N]
+// item b: d0 = a0 b0 (+ add0), d1 = a0 b1 + a1 b0 (+ add1), d2 = a1 b1 on limbs 0..level; operands a.p[b], b.p[b] may sit
+// at a higher level (component strides in elements); d0/d1/d2 are [n][level+1][N]; add (optional): item z at
+// add + z*add_bstride, [2][level+1][N]
 __global__ __launch_bounds__(PW_THREADS) void tensor_kernel(PtrList8 a, size_t a_cstride, PtrList8 b, size_t b_cstride,
                                                             u64* __restrict__ d0, u64* __restrict__ d1, u64* __restrict__ d2,
+                                                            const u64* __restrict__ add, size_t add_bstride,
                                                             const ModConst* __restrict__ mc, u32 N, u32 level) {
     const u32 x = blockIdx.x * PW_THREADS + threadIdx.x;
     if (x >= N) return;
@@ -138,18 +140,26 @@ __global__ __launch_bounds__(PW_THREADS) void tensor_kernel(PtrList8 a, size_t a
     const u64* pb = b.p[z];
     const u64 a0 = pa[o], a1 = pa[a_cstride + o], b0 = pb[o], b1 = pb[b_cstride + o];
     const size_t oo = ((size_t)z * (level + 1) + i) * N + x;
-    d0[oo] = mulmod_barrett(a0, b0, m);
+    u64 r0 = mulmod_barrett(a0, b0, m);
     U128 s = mul_wide(a0, b1);
     acc_wide(s, a1, b0);
-    d1[oo] = barrett_reduce(s, m);
+    u64 r1 = barrett_reduce(s, m);
+    if (add) {
+        const u64* ad = add + z * add_bstride;
+        r0 = add_mod(r0, ad[o], m.q);
+        r1 = add_mod(r1, ad[(size_t)(level + 1) * N + o], m.q);
+    }
+    d0[oo] = r0;
+    d1[oo] = r1;
     d2[oo] = mulmod_barrett(a1, b1, m);
 }
 
 hipError_t launch_tensor(const ckks_ctx* c, u32 level, const PtrList8& a, size_t a_cstride, const PtrList8& b, size_t b_cstride,
-                         u64* d0, u64* d1, u64* d2, u32 n, hipStream_t st) {
+                         u64* d0, u64* d1, u64* d2, u32 n, const u64* add, size_t add_bstride, hipStream_t st) {
     dim3 grid((c->N + PW_THREADS - 1) / PW_THREADS, level + 1, n);
-    ProfScope ps__(c, K_TENSOR, st, 56.0 * n * c->N * (level + 1.0), 4.0 * n * c->N * (level + 1.0));
-    hipLaunchKernelGGL(tensor_kernel, grid, dim3(PW_THREADS), 0, st, a, a_cstride, b, b_cstride, d0, d1, d2, c->d_mc, c->N, level);
+    ProfScope ps__(c, K_TENSOR, st, (56.0 + (add ? 16.0 : 0.0)) * n * c->N * (level + 1.0), 4.0 * n * c->N * (level + 1.0));
+    hipLaunchKernelGGL(tensor_kernel, grid, dim3(PW_THREADS), 0, st, a, a_cstride, b, b_cstride, d0, d1, d2, add, add_bstride, c->d_mc,
+                       c->N, level);
     return hipGetLastError();
 }
 

@@ -103,7 +103,7 @@ def test_cfg4_resnet20_stage1_conv():
 def test_cfg5_resnet20_stage3_block_slice():
     """64 -> 64 channels on 8x8 images, batch 512, 24 limbs + 8 special primes, then the degree-7
     activation on all 64 channels: the launch configuration bench.py times.  The oracle cannot
-    afford the 512 rotations, so: every conv output (deferred-ModDown schedule, as timed) decrypted
+    afford the 512 rotations, so: every conv output (deferred schedule with merged division, as timed) decrypted
     against the float64 convolution (1e-4) and every activation output against the float64 polynomial
     (1e-3); limb-for-limb parity of the activation on sampled channels (computed by the oracle from the
     GPU's conv output), and of the whole conv, in the direct and in the deferred schedule, on an 8 -> 3
@@ -126,11 +126,11 @@ def test_cfg5_resnet20_stage3_block_slice():
     d_cts = [hx.from_host(c) for c in cts]
     conv = hx.he_conv_batched(ctx, wl.height, wl.width, wl.batch, level, d_cts, dkeys, d_masks_ext,
                               hx.from_host(w_residues(w_int, ext_moduli, len(ext_moduli) - 1)), wl.c_out,
-                              alignment=hx.HE_CONV_DEFERRED_MODDOWN)
+                              alignment=hx.HE_CONV_DEFERRED_MERGED)
     scale = 2.0 ** 50
     plan = orc.act_schedule(level - 1, scale)
     d_rlk = hx.ckks_key_load(ctx, hx.from_host(rlk), 0)
-    act = hx.he_poly_act_deg7(ctx, conv, level - 1, plan["k"], d_rlk)
+    act = hx.he_poly_act_deg7(ctx, conv, level - 1, plan["k"], d_rlk, merged=True)
     ref = conv2d_reference(img, w)
     ref_max = float(np.abs(ref).max())
     assert ref_max < 1.0, ref_max
@@ -143,8 +143,10 @@ def test_cfg5_resnet20_stage3_block_slice():
     assert worst_conv < 1e-4, worst_conv
     assert worst_act < 1e-3, worst_act
     for o in (0, 41):
-        want = orc.poly_activation(hx.to_host(conv[o]), level - 1, plan["k"], rlk)
+        want = orc.poly_activation_merged(hx.to_host(conv[o]), level - 1, plan["k"], rlk)
         assert np.array_equal(hx.to_host(act[o]), want), f"activation of channel {o}"
+    two_step = hx.he_poly_act_deg7(ctx, [conv[7]], level - 1, plan["k"], d_rlk)          # the two-step variant on one channel
+    assert np.array_equal(hx.to_host(two_step[0]), orc.poly_activation(hx.to_host(conv[7]), level - 1, plan["k"], rlk))
     # an 8 -> 3 channel slice of the same layer, limb for limb
     sub_in, sub_out = list(range(8)), [5, 20, 63]
     w_sub = w_int[np.ix_(sub_out, sub_in)]
@@ -155,12 +157,12 @@ def test_cfg5_resnet20_stage3_block_slice():
         assert np.array_equal(hx.to_host(got[i]), want[i]), f"slice output {i}"
     # the same slice in the deferred schedule, limb for limb, and equal to the full run's channels where the
     # inputs coincide is not expected (other input channels): compare with the oracle only
-    got = hx.he_conv_batched(ctx, wl.height, wl.width, wl.batch, level, [d_cts[c] for c in sub_in], dkeys, d_masks_ext,
-                             hx.from_host(w_residues(w_sub, ext_moduli, len(ext_moduli) - 1)), len(sub_out),
-                             alignment=hx.HE_CONV_DEFERRED_MODDOWN)
-    want = orc.he_conv_deferred([cts[c] for c in sub_in], level, wl.width, keys, masks_ext, w_sub)
-    for i in range(len(sub_out)):
-        assert np.array_equal(hx.to_host(got[i]), want[i]), f"deferred slice output {i}"
+    for mode, merged in ((hx.HE_CONV_DEFERRED_MODDOWN, False), (hx.HE_CONV_DEFERRED_MERGED, True)):
+        got = hx.he_conv_batched(ctx, wl.height, wl.width, wl.batch, level, [d_cts[c] for c in sub_in], dkeys, d_masks_ext,
+                                 hx.from_host(w_residues(w_sub, ext_moduli, len(ext_moduli) - 1)), len(sub_out), alignment=mode)
+        want = orc.he_conv_deferred([cts[c] for c in sub_in], level, wl.width, keys, masks_ext, w_sub, merged=merged)
+        for i in range(len(sub_out)):
+            assert np.array_equal(hx.to_host(got[i]), want[i]), f"deferred slice output {i} (merged division: {merged})"
 
 
 def test_accumulator_merge_at_the_block_group_transition():

@@ -133,7 +133,7 @@ def test_ctct_mul_relin_matches_oracle(ks_setup, level):
 
 
 # ----------------------------------------------------------------------------------- convolution
-def conv_case(name, level=None, bits=50, four_keys=False, deferred=False):
+def conv_case(name, level=None, bits=50, four_keys=False, deferred=False, merged=False):
     wl = CONFIGS[name]
     p = make_params(wl.log_n, wl.num_q, wl.num_p, wl.dnum, bits=bits)
     orc, ctx = both(p)
@@ -149,6 +149,8 @@ def conv_case(name, level=None, bits=50, four_keys=False, deferred=False):
     masks, w_int = operands(w, wl.height, wl.width, wl.batch, level, 2.0 ** 28, p.moduli[level] / 2.0 ** 28)
     w_moduli = [p.moduli[t] for t in orc.ext_moduli_idx(level)] if deferred else p.moduli
     mode = hx.HE_CONV_DEFERRED_MODDOWN if deferred else (hx.HE_CONV_ALIGN_FOUR_KEYS if four_keys else hx.HE_CONV_ALIGN_DIRECT)
+    if merged:
+        mode = hx.HE_CONV_DEFERRED_MERGED
     if four_keys:                                 # only the keys of -1, +1, -W, +W exist
         keys = {off: k for off, k in keys.items() if off in (-1, 1, -wl.width, wl.width)}
     dkeys = [hx.ckks_key_load(ctx, hx.from_host(keys[off]), hx.ckks_galois_element(ctx, off)) if off in keys else None for off in offs]
@@ -194,6 +196,19 @@ def test_he_conv_deferred_moddown_matches_oracle(name, level, bits):
     oracle's deferred schedule, same slots as the float64 convolution."""
     wl, p, orc, level, s_ntt, img, w, scale, cts, keys, masks, w_int, outs = conv_case(name, level, bits, deferred=True)
     want = orc.he_conv_deferred(cts, level, wl.width, keys, masks, w_int)
+    ref = conv2d_reference(img, w)
+    for o in range(wl.c_out):
+        assert np.array_equal(outs[o], want[o]), f"output channel {o}"
+        dec = orc.unpack_channel(orc.decrypt(outs[o], level - 1, s_ntt, scale), wl.batch, wl.height, wl.width)
+        assert np.abs(dec - ref[:, o]).max() < 1e-4
+
+
+@pytest.mark.parametrize("name,level,bits", [("cfg1_single_conv", None, 50), ("small_conv", None, 50), ("small_conv", 1, 50),
+                                             ("small_conv", 3, 56)])
+def test_he_conv_deferred_merged_division_matches_oracle(name, level, bits):
+    """The deferred schedule with ModDown and rescale of every sum as one division by P*q_level."""
+    wl, p, orc, level, s_ntt, img, w, scale, cts, keys, masks, w_int, outs = conv_case(name, level, bits, deferred=True, merged=True)
+    want = orc.he_conv_deferred(cts, level, wl.width, keys, masks, w_int, merged=True)
     ref = conv2d_reference(img, w)
     for o in range(wl.c_out):
         assert np.array_equal(outs[o], want[o]), f"output channel {o}"
@@ -302,6 +317,28 @@ def test_poly_activation_matches_oracle(n_ct):
     for i in range(n_ct):
         got = hx.to_host(outs[i])
         assert np.array_equal(got, orc.poly_activation(cts[i], level, plan["k"], rlk)), f"channel {i}"
+        dec = orc.decrypt(got, plan["out_level"], s_ntt, plan["out_scale"])
+        assert np.abs(dec - activation_reference(xs[i])).max() < 1e-3
+
+
+@pytest.mark.parametrize("n_ct,bits", [(1, 50), (10, 50), (2, 56)])
+def test_poly_activation_merged_division_matches_oracle(n_ct, bits):
+    wl = CONFIGS["small_block"]
+    p = make_params(wl.log_n, wl.num_q, wl.num_p, wl.dnum, bits=bits)
+    orc, ctx = both(p)
+    level = p.num_q - 1
+    s, s_ntt = orc.gen_secret(351)
+    rlk = orc.gen_relin_key(s_ntt, 352)
+    rng = np.random.default_rng(353)
+    scale = float(2 ** (bits - 1)) if bits > 50 else 2.0 ** 50
+    plan = orc.act_schedule(level, scale)
+    xs = [rng.uniform(-1, 1, orc.n) for _ in range(n_ct)]
+    cts = [orc.encrypt(x, scale, level, s_ntt, 354 + i) for i, x in enumerate(xs)]
+    outs = hx.he_poly_act_deg7(ctx, [hx.from_host(ct) for ct in cts], level, plan["k"], hx.ckks_key_load(ctx, hx.from_host(rlk), 0),
+                               merged=True)
+    for i in range(n_ct):
+        got = hx.to_host(outs[i])
+        assert np.array_equal(got, orc.poly_activation_merged(cts[i], level, plan["k"], rlk)), f"channel {i}"
         dec = orc.decrypt(got, plan["out_level"], s_ntt, plan["out_scale"])
         assert np.abs(dec - activation_reference(xs[i])).max() < 1e-3
 
