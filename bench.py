@@ -26,13 +26,14 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# vector integer peak: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3e12 32-bit lane-operations/s
+# vector ALU peak: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3e12 lane-operations/s (32-bit integer or fp64 FMA alike)
 ALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
-# kernels whose limiter is instruction issue, with the 32-bit lane-operations one unit of their work
-# needs at the very least (derivations in the design doc): a 64-bit Shoup butterfly = 10 multiplies + 13
-# add/carry operations; one multiply-add of the carry-free 25-bit-split accumulation = 3 multiply-adds
-ALU_KERNELS = {"ntt_fwd_lo": (23.0, "Gbutterfly/s"), "ntt_inv_lo": (23.0, "Gbutterfly/s"),
-               "weighted_sum": (3.0, "Gmodmac/s")}
+# Kernels whose limiter is arithmetic, should one of them become the dominant kernel (derivations in the design doc):
+# a double-precision butterfly of the NTT = 10 fp64 operations (6 for the twiddle product, 2 for sum and
+# difference, 2 for the amortised re-centring); the multiply-accumulate on the matrix cores = 49 digit
+# products x 2 operations per modular multiply-add against the dense 8-bit integer peak.
+ALU_KERNELS = {"ntt_fwd_lo": (10.0, "Gbutterfly/s"), "ntt_inv_lo": (10.0, "Gbutterfly/s")}
+MFMA_KERNELS = {"weighted_sum": (98.0, 5.0e15)}   # int8 operations per modular multiply-add, peak int8 op/s
 TRAFFIC_FILE = os.path.join(ROOT, "profiles", "pmc_traffic_cfg5_block_slice.txt")
 
 
@@ -220,7 +221,11 @@ def main():
         roof = {"kernel": dom, "launches": v["launches"], "avg_us": 1e6 * secs / v["launches"],
                 "algorithmic_bytes_per_launch": v["bytes"] / v["launches"], "traffic": traffic,
                 "hbm_GBs": v["bytes"] / secs / 1e9}
-        if dom in ALU_KERNELS:
+        if dom in MFMA_KERNELS:
+            per, peak_ops = MFMA_KERNELS[dom]
+            ach = v["ops"] * per / secs / 1e12
+            roof.update({"bound": "mfma", "achieved": ach, "peak": peak_ops / 1e12, "unit": "TOP/s (int8)", "frac": ach / (peak_ops / 1e12)})
+        elif dom in ALU_KERNELS:
             lane_ops, unit = ALU_KERNELS[dom]
             peak = ALU_PEAK_LANE_OPS / lane_ops / 1e9
             ach = v["ops"] / secs / 1e9
