@@ -233,29 +233,47 @@ int conv_deferred(const ckks_ctx* c, const he_conv_desc* d, const u32* gs, const
     u64* acc = ar.take((size_t)d->c_out * x_elems);
     u64* wscratch = ar.take(weighted_sum_scratch_elems(c, E, d->c_in * 9, d->c_out));
     u64* tmp = ar.take((size_t)CT_BATCH * ct_elems);
+    u64* kscratch = ar.take(key_inner_taps_scratch_elems(c, level, 8));
+    // the aligned copies are stored term-innermost when the fused inner product can write them that way
+    const bool fused_taps = c->live_digits(level) <= 4;
+    const XLayout xl = (fused_taps && N % 64 == 0) ? XLayout::tiled((size_t)d->c_in * 9, N) : XLayout::classic(E, N);
     if (!ok || !ar.ok() || ar.used + ws_rescale(c, level, CT_BATCH) > ar.cap)
         return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for the convolution");
     for (u32 c0 = 0; c0 < d->c_in; c0 += CT_BATCH) {
         const u32 n = d->c_in - c0 < CT_BATCH ? d->c_in - c0 : CT_BATCH;
         const u64 *in[CT_BATCH], *c1s[CT_BATCH];
-        u64* outs[CT_BATCH];
         for (u32 b = 0; b < n; b++) {
             in[b] = (const u64*)h_d_in[c0 + b];
             c1s[b] = in[b] + L1 * N;
         }
         int rc = run_modup(c, level, c1s, n, ws, st);
         if (rc) return rc;
+        // taps without a rotation (the centre) are a product with the mask; all the others go through one launch
+        const u64 *tkeys[8], *tmasks[8];
+        u32 tg[8], ttap[8], n_taps = 0;
         for (u32 t = 0; t < 9; t++) {
             const u64* mask = masks + (size_t)t * E * N;
-            for (u32 b = 0; b < n; b++) outs[b] = xs + ((size_t)(c0 + b) * 9 + t) * x_elems;
             if (gs[t] == 1) {
-                for (u32 b = 0; b < n; b++) HIP_TRY(launch_centre_ext(c, level, mask, in[b], outs[b], st));
+                for (u32 b = 0; b < n; b++) HIP_TRY(launch_centre_ext(c, level, mask, in[b], xs, xl, (c0 + b) * 9 + t, st));
                 continue;
             }
-            HIP_TRY(launch_key_inner_ext(c, level, ws.digits, ws.dig_b, rot_keys[t]->d_key, gs[t], in, nullptr, mask, outs, n, st));
+            tkeys[n_taps] = rot_keys[t]->d_key;
+            tmasks[n_taps] = mask;
+            tg[n_taps] = gs[t];
+            ttap[n_taps++] = t;
+        }
+        if (fused_taps) {
+            HIP_TRY(launch_key_inner_taps(c, level, ws.digits, ws.dig_b, tkeys, tg, tmasks, ttap, n_taps, in, xs, xl, c0 * 9, 9, n, kscratch,
+                                          c0 == 0, st));  // the masked keys are made once, by the first batch
+        } else {  // many digits: one launch per tap (classic layout: every term is a [2][E][N] array)
+            for (u32 i = 0; i < n_taps; i++) {
+                u64* outs[CT_BATCH];
+                for (u32 b = 0; b < n; b++) outs[b] = xs + ((size_t)(c0 + b) * 9 + ttap[i]) * x_elems;
+                HIP_TRY(launch_key_inner_ext(c, level, ws.digits, ws.dig_b, tkeys[i], tg[i], in, nullptr, tmasks[i], outs, n, st));
+            }
         }
     }
-    HIP_TRY(launch_weighted_sum(c, level, true, xs, d->c_in * 9, w_res, d->c_out, acc, wscratch, st));
+    HIP_TRY(launch_weighted_sum(c, level, true, xs, xl, d->c_in * 9, w_res, d->c_out, acc, wscratch, st));
     for (u32 o0 = 0; o0 < d->c_out; o0 += CT_BATCH) {
         const u32 n = d->c_out - o0 < CT_BATCH ? d->c_out - o0 : CT_BATCH;
         KsWs wd = ws;
@@ -301,7 +319,7 @@ size_t he_conv_workspace_bytes(const ckks_ctx* c, const he_conv_desc* d) {
         const size_t E = c->ext_limbs(d->level);
         return ws_ks(c, d->level, CT_BATCH, CT_BATCH) + blk((size_t)d->c_in * 9 * 2 * E * N) + blk((size_t)d->c_out * 2 * E * N) +
                blk(weighted_sum_scratch_elems(c, (u32)E, d->c_in * 9, d->c_out)) + blk((size_t)CT_BATCH * 2 * L1 * N) +
-               ws_rescale(c, d->level, CT_BATCH);
+               blk(key_inner_taps_scratch_elems(c, d->level, 8)) + ws_rescale(c, d->level, CT_BATCH);
     }
     return ws_ks(c, d->level, CT_BATCH, CT_BATCH) + blk((size_t)d->c_in * 9 * 2 * L1 * N) + blk((size_t)d->c_out * 2 * L1 * N) +
            blk(weighted_sum_scratch_elems(c, (u32)L1, d->c_in * 9, d->c_out)) + ws_rescale(c, d->level, CT_BATCH) +
@@ -612,7 +630,7 @@ int he_conv_batched(const ckks_ctx* c, const he_conv_desc* d, const uint64_t* co
         }
     }
     // convolution evaluation: integer-weighted sum over (input channel, tap) for every output channel
-    HIP_TRY(launch_weighted_sum(c, level, false, xs, d->c_in * 9, (const u64*)d_w_res, d->c_out, acc, wscratch, st));
+    HIP_TRY(launch_weighted_sum(c, level, false, xs, XLayout::classic(L1, N), d->c_in * 9, (const u64*)d_w_res, d->c_out, acc, wscratch, st));
     for (u32 o0 = 0; o0 < d->c_out; o0 += CT_BATCH) {
         const u32 n = d->c_out - o0 < CT_BATCH ? d->c_out - o0 : CT_BATCH;
         const u64* ins[CT_BATCH];

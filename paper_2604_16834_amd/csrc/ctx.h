@@ -61,6 +61,19 @@ struct OutList8 {
     u64* p[KS_MAX_BATCH];
 };
 
+// Where element (term k, component comp, limb e, point x) of the operands of the layer's multiply-accumulate
+// lives:  base + k*s_k + comp*s_comp + e*s_e + (x >> 6)*s_xt + (x & 63).  Two layouts:
+//   classic  [k][comp][limb][N]: every term is a ciphertext-shaped array (s_k = 2*nl*N, s_comp = nl*N, s_e = N, s_xt = 64)
+//   tiled    [limb][comp][N/64][k][64]: all terms of one (limb, component, 64 points) are one contiguous run, which
+//            is what one workgroup of the matrix-core kernel consumes and what one wavefront of the fused inner
+//            product scatters into (s_k = 64, s_xt = 64*K, s_comp = N*K, s_e = 2*N*K); needs N % 64 == 0
+struct XLayout {
+    size_t s_k, s_comp, s_e, s_xt;
+    __host__ __device__ size_t at(size_t k, u32 comp, u32 e, u32 x) const { return k * s_k + comp * s_comp + e * s_e + (size_t)(x >> 6) * s_xt + (x & 63); }
+    static XLayout classic(size_t nl, size_t N) { return XLayout{2 * nl * N, nl * N, N, 64}; }
+    static XLayout tiled(size_t K, size_t N) { return XLayout{64, N * K, 2 * N * K, 64 * K}; }
+};
+
 // One key switch of a batch, as its last kernel sees it (see moddown_final_kernel).
 struct FinalItem {
     const u64* add0;
@@ -159,6 +172,11 @@ hipError_t launch_key_inner_multi(const ckks_ctx* c, u32 level, const u64* digit
 hipError_t launch_key_inner_ext(const ckks_ctx* c, u32 level, const u64* digits, size_t digits_bstride, const u64* key, u32 g,
                                 const u64* const* add0s, const u64* const* add1s, const u64* mask, u64* const* outs, u32 n,
                                 hipStream_t st);
+// result of (item b, tap i) = term k0 + b*k_bstride + taps[i] of `xs` in layout xl
+hipError_t launch_key_inner_taps(const ckks_ctx* c, u32 level, const u64* digits, size_t digits_bstride, const u64* const* keys,
+                                 const u32* gs, const u64* const* masks, const u32* taps, u32 n_taps, const u64* const* c0s,
+                                 u64* xs, XLayout xl, u32 k0, u32 k_bstride, u32 n, u64* scratch, bool prepare, hipStream_t st);
+size_t key_inner_taps_scratch_elems(const ckks_ctx* c, u32 level, u32 n_taps);
 // merged: the dropped limbs are q_level and the special primes (division by P*q_level, results on limbs 0..level-1)
 hipError_t launch_moddown_conv(const ckks_ctx* c, u32 level, bool merged, const u64* v, u64* w, u32 batch, hipStream_t st);
 hipError_t launch_moddown_final(const ckks_ctx* c, u32 level, bool merged, const u64* v, const u64* w, const FinalItem* items, u32 n,
@@ -175,15 +193,15 @@ hipError_t launch_tensor(const ckks_ctx* c, u32 level, const PtrList8& a, size_t
                          u64* d0, u64* d1, u64* d2, u32 n, const u64* add, size_t add_bstride, hipStream_t st);
 hipError_t launch_mask_mul(const ckks_ctx* c, u32 level, const u64* mask, const u64* ct, u64* out, hipStream_t st);
 hipError_t launch_ct_sum(const ckks_ctx* c, u32 level, const PtrList8& items, u32 n, u64* out, hipStream_t st);
-hipError_t launch_centre_ext(const ckks_ctx* c, u32 level, const u64* mask, const u64* ct, u64* out, hipStream_t st);
+hipError_t launch_centre_ext(const ckks_ctx* c, u32 level, const u64* mask, const u64* ct, u64* xs, XLayout xl, u32 k, hipStream_t st);
 size_t weighted_sum_scratch_elems(const ckks_ctx* c, u32 n_limbs, u32 n_terms, u32 c_out);
-hipError_t launch_weighted_sum(const ckks_ctx* c, u32 level, bool extended, const u64* xs, u32 n_terms, const u64* w_res, u32 c_out,
-                               u64* acc, u64* scratch, hipStream_t st);
+hipError_t launch_weighted_sum(const ckks_ctx* c, u32 level, bool extended, const u64* xs, XLayout xl, u32 n_terms, const u64* w_res,
+                               u32 c_out, u64* acc, u64* scratch, hipStream_t st);
 // wsum_mfma.hip
 bool wsum_mfma_applies(const ckks_ctx* c, u32 n_terms);
 size_t wsum_mfma_scratch_elems(u32 n_limbs, u32 n_terms, u32 c_out);
-hipError_t launch_wsum_mfma(const ckks_ctx* c, u32 level, u32 nl, const u64* xs, u32 n_terms, const u64* w_res, u32 c_out, u64* acc,
-                            u64* scratch, hipStream_t st);
+hipError_t launch_wsum_mfma(const ckks_ctx* c, u32 level, u32 nl, const u64* xs, XLayout xl, u32 n_terms, const u64* w_res, u32 c_out,
+                            u64* acc, u64* scratch, hipStream_t st);
 hipError_t launch_lincomb2(const ckks_ctx* c, u32 level, const PtrList8& a, size_t a_cstride, const u64* ka, const PtrList8& b,
                            size_t b_cstride, const u64* kb, const u64* add, size_t add_bstride, u64* out, size_t out_bstride, u32 n,
                            hipStream_t st);

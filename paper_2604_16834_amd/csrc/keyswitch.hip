@@ -325,6 +325,180 @@ hipError_t launch_key_inner_ext(const ckks_ctx* c, u32 level, const u64* digits,
     return hipGetLastError();
 }
 
+// All the taps of a convolution for a batch of input channels in one launch: the same arithmetic as
+// key_inner_ext_kernel (P * sigma_g(c0) added, tap mask multiplied in) for up to 8 (key, Galois element,
+// mask) triples, organised by SOURCE point: a thread loads the digits and c0 of one evaluation point of
+// every batch item once (coalesced) and, for each tap, sends them to the point sigma_g^-1 maps it to,
+// where it reads the key and the mask and writes the result.  sigma_g maps every aligned run of 2^m
+// points onto an aligned run of 2^m points, so a wavefront's 64 destinations are one 512-byte run,
+// permuted inside: key reads and result writes are as coalesced as unpermuted ones.  The digits stream
+// from HBM once per batch instead of once per tap, with no reliance on a cache.
+// result of (item b, tap i): term k0 + b * k_bstride + tap[i] of xs in layout xl
+struct TapSet {
+    const u64* key[8];
+    const u64* mask[8];
+    u32 ginv[8];  // inverse Galois elements: the destination of source point x under sigma_g is gather(x, g^-1)
+    u32 tap[8];
+    u32 n_taps;
+};
+
+// The tap's mask is folded into the key before the batch runs: mk[i][j][comp][e][x] = mask_i[e][x] * key_i[j][comp][t(e)][x]
+// on the live digits and limbs, mp[i][e][x] = mask_i[e][x] * [P]_{q_e} for e <= level.  Then
+//   mask * (sum_j d_j key_j + P c0) = sum_j d_j mk_j + c0 mp
+// is one unreduced sum with one reduction per result: the per-result mask product (half of the arithmetic)
+// is gone.  Costs one pass over the eight keys per call.
+__global__ __launch_bounds__(KS_THREADS) void mask_keys_kernel(TapSet T, u64* __restrict__ mk, u64* __restrict__ mp,
+                                                               const u64* __restrict__ negp, const ModConst* __restrict__ mc, u32 N,
+                                                               u32 level, u32 num_q, u32 M, u32 E, u32 beta) {
+    const u32 x = blockIdx.x * KS_THREADS + threadIdx.x;
+    if (x >= N) return;
+    const u32 e = blockIdx.y, i = blockIdx.z;
+    const u32 t = e <= level ? e : num_q + (e - level - 1);
+    const ModConst m = mc[t];
+    const u64 mv = T.mask[i][(size_t)e * N + x];
+    for (u32 j = 0; j < beta; j++)
+        for (u32 comp = 0; comp < 2; comp++)
+            mk[((((size_t)i * beta + j) * 2 + comp) * E + e) * N + x] = mulmod_barrett(mv, T.key[i][(((size_t)j * 2 + comp) * M + t) * N + x], m);
+    if (e <= level) mp[((size_t)i * (level + 1) + e) * N + x] = mulmod_barrett(mv, m.q - negp[e], m);
+}
+
+// SMALL: every modulus below 2^50 (carry-free 25-bit-split accumulation, three multiply-adds per product).
+template <int BETA, bool SMALL>
+__global__ __launch_bounds__(KS_THREADS) void key_inner_taps_kernel(const u64* __restrict__ digits, size_t digits_bstride, TapSet T,
+                                                                    const u64* __restrict__ mk, const u64* __restrict__ mp,
+                                                                    PtrList8 c0s, u64* __restrict__ xs, XLayout xl, u32 k0base,
+                                                                    u32 k_bstride, const ModConst* __restrict__ mc, u32 log_n,
+                                                                    u32 level, u32 num_q, u32 E, u32 n) {
+    const u32 N = 1u << log_n;
+    const u32 xsrc = blockIdx.x * KS_THREADS + threadIdx.x;
+    if (xsrc >= N) return;
+    const u32 e = blockIdx.y;
+    const ModConst m = mc[e <= level ? e : num_q + (e - level - 1)];
+    const bool has_add = e <= level;
+    u64 dv[CT_BATCH][BETA], cv[CT_BATCH];
+#pragma unroll
+    for (u32 b = 0; b < CT_BATCH; b++) {
+        const bool on = b < n;
+        cv[b] = (on && has_add) ? c0s.p[b][(size_t)e * N + xsrc] : 0;
+#pragma unroll
+        for (u32 j = 0; j < BETA; j++) dv[b][j] = on ? digits[b * digits_bstride + ((size_t)j * E + e) * N + xsrc] : 0;
+    }
+    for (u32 i = 0; i < T.n_taps; i++) {
+        const u32 x = galois_gather_index(xsrc, T.ginv[i], log_n);  // destination point
+        u64 k0[BETA], k1[BETA];
+#pragma unroll
+        for (u32 j = 0; j < BETA; j++) {
+            k0[j] = mk[((((size_t)i * BETA + j) * 2 + 0) * E + e) * N + x];
+            k1[j] = mk[((((size_t)i * BETA + j) * 2 + 1) * E + e) * N + x];
+        }
+        const u64 kp = has_add ? mp[((size_t)i * (level + 1) + e) * N + x] : 0;
+        u64* ot = xs + xl.at(k0base + T.tap[i], 0, e, x);
+        if (SMALL) {
+            Split50 s0[BETA], s1[BETA];
+#pragma unroll
+            for (u32 j = 0; j < BETA; j++) { s0[j] = split50(k0[j]); s1[j] = split50(k1[j]); }
+            const Split50 sp = split50(kp);
+#pragma unroll
+            for (u32 b = 0; b < CT_BATCH; b++) {
+                if (b < n) {
+                    Acc50 a0 = {0, 0, 0}, a1 = {0, 0, 0};
+#pragma unroll
+                    for (u32 j = 0; j < BETA; j++) {
+                        const Split50 d = split50(dv[b][j]);
+                        acc50_mad(a0, d, s0[j]);
+                        acc50_mad(a1, d, s1[j]);
+                    }
+                    acc50_mad(a0, split50(cv[b]), sp);
+                    u64* ob = ot + (size_t)b * k_bstride * xl.s_k;
+                    ob[0] = barrett_reduce(acc50_value(a0), m);
+                    ob[xl.s_comp] = barrett_reduce(acc50_value(a1), m);
+                }
+            }
+        } else {
+#pragma unroll
+            for (u32 b = 0; b < CT_BATCH; b++) {
+                if (b < n) {
+                    U128 acc0 = {0, 0}, acc1 = {0, 0};
+#pragma unroll
+                    for (u32 j = 0; j < BETA; j++) {
+                        acc_wide(acc0, dv[b][j], k0[j]);
+                        acc_wide(acc1, dv[b][j], k1[j]);
+                    }
+                    acc_wide(acc0, cv[b], kp);
+                    u64* ob = ot + (size_t)b * k_bstride * xl.s_k;
+                    ob[0] = barrett_reduce(acc0, m);
+                    ob[xl.s_comp] = barrett_reduce(acc1, m);
+                }
+            }
+        }
+    }
+}
+
+// words of scratch launch_key_inner_taps needs (the masked keys)
+size_t key_inner_taps_scratch_elems(const ckks_ctx* c, u32 level, u32 n_taps) {
+    return (size_t)n_taps * c->N * ((size_t)c->live_digits(level) * 2 * c->ext_limbs(level) + level + 1);
+}
+
+// keys / gs / masks / taps: n_taps <= 8 entries (taps[i] = position of tap i in the output's tap stride);
+// c0s: n <= CT_BATCH device pointers [level+1][N]; scratch: key_inner_taps_scratch_elems() words, filled by
+// prepare (once per set of taps) and read by every later call with prepare = false.
+// Needs beta <= 4 (returns hipErrorNotSupported otherwise: the caller then falls back to one launch per tap).
+hipError_t launch_key_inner_taps(const ckks_ctx* c, u32 level, const u64* digits, size_t digits_bstride, const u64* const* keys,
+                                 const u32* gs, const u64* const* masks, const u32* taps, u32 n_taps, const u64* const* c0s,
+                                 u64* xs, XLayout xl, u32 k0, u32 k_bstride, u32 n, u64* scratch, bool prepare, hipStream_t st) {
+    if (n_taps == 0 || n == 0) return hipSuccess;
+    if (n_taps > 8 || n > CT_BATCH) return hipErrorInvalidValue;
+    const u32 E = c->ext_limbs(level), beta = c->live_digits(level);
+    if (beta > 4) return hipErrorNotSupported;
+    TapSet T;
+    const u64 two_n = 2ull * c->N;
+    for (u32 i = 0; i < 8; i++) {
+        T.key[i] = i < n_taps ? keys[i] : nullptr;
+        T.mask[i] = i < n_taps ? masks[i] : nullptr;
+        T.tap[i] = i < n_taps ? taps[i] : 0;
+        u64 inv = 1;
+        if (i < n_taps) {  // g^-1 mod 2N: g is odd, the group has exponent N/2
+            u64 base = gs[i] % two_n;
+            for (u64 ex = c->N / 2 - 1; ex; ex >>= 1) {
+                if (ex & 1) inv = inv * base % two_n;
+                base = base * base % two_n;
+            }
+        }
+        T.ginv[i] = (u32)inv;
+    }
+    T.n_taps = n_taps;
+    PtrList8 cl;
+    for (u32 b = 0; b < KS_MAX_BATCH; b++) cl.p[b] = b < n ? c0s[b] : nullptr;
+    u64* mk = scratch;
+    u64* mp = scratch + (size_t)n_taps * beta * 2 * E * c->N;
+    const u32 nxb = (c->N + KS_THREADS - 1) / KS_THREADS;
+    if (prepare) {
+        const u64* negp = c->d_moddown + 2 * c->k_pad + (size_t)c->k_pad * c->num_q + 2 * c->num_q;
+        ProfScope ps__(c, K_MASK_MUL, st, 8.0 * c->N * n_taps * (E * (4.0 * beta + 1.0) + level + 1.0), 2.0 * c->N * n_taps * E * beta);
+        hipLaunchKernelGGL(mask_keys_kernel, dim3(nxb, E, n_taps), dim3(KS_THREADS), 0, st, T, mk, mp, negp, c->d_mc, c->N, level, c->num_q,
+                           c->M, E, beta);
+    }
+    dim3 grid(nxb, E);
+    // digits and c0 once per batch, per tap one masked key and the outputs
+    ProfScope ps__(c, K_KEY_INNER, st, 8.0 * c->N * (E * (n * (double)beta + n_taps * (2.0 * beta + 2.0 * n)) + (n + n_taps) * (level + 1.0)),
+                   2.0 * n_taps * n * c->N * E * (beta + 1.0));
+#define KI_TAPS(B_)                                                                                                                  \
+    do {                                                                                                                             \
+        if (c->small_q)                                                                                                              \
+            hipLaunchKernelGGL((key_inner_taps_kernel<B_, true>), grid, dim3(KS_THREADS), 0, st, digits, digits_bstride, T, mk, mp, cl, xs, xl, \
+                               k0, k_bstride, c->d_mc, c->log_n, level, c->num_q, E, n);                                             \
+        else                                                                                                                         \
+            hipLaunchKernelGGL((key_inner_taps_kernel<B_, false>), grid, dim3(KS_THREADS), 0, st, digits, digits_bstride, T, mk, mp, cl, xs, xl, \
+                               k0, k_bstride, c->d_mc, c->log_n, level, c->num_q, E, n);                                             \
+    } while (0)
+    if (beta == 1) KI_TAPS(1);
+    else if (beta == 2) KI_TAPS(2);
+    else if (beta == 3) KI_TAPS(3);
+    else KI_TAPS(4);
+#undef KI_TAPS
+    return hipGetLastError();
+}
+
 // ---- ModDown, conversion of the P-part ----------------------------------------------------------
 // v [2][E][N]: limbs level+1.. hold the P-part in coefficient form.  w [2][level+1][N] (coefficients)
 #define MODDOWN_LIMBS_PER_BLOCK 12

@@ -181,9 +181,9 @@ hipError_t launch_mask_mul(const ckks_ctx* c, u32 level, const u64* mask, const 
 }
 
 // The centre tap of a convolution that divides by P after its sum: out[comp][e] = mask[e] * [P]_{q_e} * ct[comp][e]
-// on the live q-limbs, zero on the special primes (out [2][E][N], mask [E][N], ct [2][level+1][N]).
+// on the live q-limbs, zero on the special primes (result = term k of xs in layout xl, mask [E][N], ct [2][level+1][N]).
 __global__ __launch_bounds__(PW_THREADS) void centre_ext_kernel(const u64* __restrict__ mask, const u64* __restrict__ ct,
-                                                                u64* __restrict__ out, const u64* __restrict__ negp,
+                                                                u64* __restrict__ xs, XLayout xl, u32 k, const u64* __restrict__ negp,
                                                                 const ModConst* __restrict__ mc, u32 N, u32 level, u32 E) {
     const u32 x = blockIdx.x * PW_THREADS + threadIdx.x;
     if (x >= N) return;
@@ -194,15 +194,15 @@ __global__ __launch_bounds__(PW_THREADS) void centre_ext_kernel(const u64* __res
         const u64 pm = mulmod_barrett(m.q - negp[e], mask[(size_t)e * N + x], m);
         r = mulmod_barrett(pm, ct[((size_t)comp * (level + 1) + e) * N + x], m);
     }
-    out[((size_t)comp * E + e) * N + x] = r;
+    xs[xl.at(k, comp, e, x)] = r;
 }
 
-hipError_t launch_centre_ext(const ckks_ctx* c, u32 level, const u64* mask, const u64* ct, u64* out, hipStream_t st) {
+hipError_t launch_centre_ext(const ckks_ctx* c, u32 level, const u64* mask, const u64* ct, u64* xs, XLayout xl, u32 k, hipStream_t st) {
     const u32 E = c->ext_limbs(level);
     const u64* negp = c->d_moddown + 2 * c->k_pad + (size_t)c->k_pad * c->num_q + 2 * c->num_q;
     dim3 grid((c->N + PW_THREADS - 1) / PW_THREADS, E, 2);
     ProfScope ps__(c, K_MASK_MUL, st, 8.0 * c->N * (3.0 * (level + 1.0) + 2.0 * E), 4.0 * c->N * (level + 1.0));
-    hipLaunchKernelGGL(centre_ext_kernel, grid, dim3(PW_THREADS), 0, st, mask, ct, out, negp, c->d_mc, c->N, level, E);
+    hipLaunchKernelGGL(centre_ext_kernel, grid, dim3(PW_THREADS), 0, st, mask, ct, xs, xl, k, negp, c->d_mc, c->N, level, E);
     return hipGetLastError();
 }
 
@@ -211,7 +211,7 @@ hipError_t launch_centre_ext(const ckks_ctx* c, u32 level, const u64* mask, cons
 // for moduli above 2^50 (the matrix-core kernel in wsum_mfma.hip takes the others): each thread keeps
 // WS_OUT_TILE output channels' 128-bit sums so that every xs element is loaded once per tile.
 #define WS_OUT_TILE 4
-__global__ __launch_bounds__(PW_THREADS) void weighted_sum_kernel(const u64* __restrict__ xs, const u64* __restrict__ w_res,
+__global__ __launch_bounds__(PW_THREADS) void weighted_sum_kernel(const u64* __restrict__ xs, XLayout xl, const u64* __restrict__ w_res,
                                                                   u64* __restrict__ acc, const ModConst* __restrict__ mc, u32 N,
                                                                   u32 level, u32 L1, u32 num_q, u32 n_terms, u32 c_out, u32 lazy_terms) {
     const u32 x = blockIdx.x * PW_THREADS + threadIdx.x;
@@ -226,7 +226,7 @@ __global__ __launch_bounds__(PW_THREADS) void weighted_sum_kernel(const u64* __r
     for (u32 t = 0; t < WS_OUT_TILE; t++) s[t] = {0, 0};
     u32 pending = 0;
     for (u32 k = 0; k < n_terms; k++) {
-        const u64 v = xs[k * ct_stride + off];
+        const u64 v = xs[xl.at(k, comp, i, x)];
 #pragma unroll
         for (u32 t = 0; t < WS_OUT_TILE; t++)
             if (o0 + t < c_out) acc_wide(s[t], v, w_res[((size_t)(o0 + t) * n_terms + k) * L1 + i]);
@@ -246,20 +246,20 @@ size_t weighted_sum_scratch_elems(const ckks_ctx* c, u32 n_limbs, u32 n_terms, u
     return 0;
 }
 
-// xs [n_terms][2][nl][N], w_res [c_out][n_terms][nl], acc [c_out][2][nl][N]; nl = level+1 (the live q-limbs) or,
+// xs: n_terms operands in layout xl, w_res [c_out][n_terms][nl], acc [c_out][2][nl][N]; nl = level+1 (the live q-limbs) or,
 // with `extended`, level+1+num_p (the extended basis: positions above `level` are the special primes).
 // scratch: weighted_sum_scratch_elems() words (may be null when that is 0)
-hipError_t launch_weighted_sum(const ckks_ctx* c, u32 level, bool extended, const u64* xs, u32 n_terms, const u64* w_res, u32 c_out,
-                               u64* acc, u64* scratch, hipStream_t st) {
+hipError_t launch_weighted_sum(const ckks_ctx* c, u32 level, bool extended, const u64* xs, XLayout xl, u32 n_terms, const u64* w_res,
+                               u32 c_out, u64* acc, u64* scratch, hipStream_t st) {
     const u32 L1 = extended ? c->ext_limbs(level) : level + 1;
     const double bytes = 16.0 * c->N * L1 * ((double)n_terms + c_out), ops = 2.0 * c->N * L1 * n_terms * c_out;
     if (wsum_mfma_applies(c, n_terms)) {  // moduli below 2^50: exact 8-bit digit products on the matrix cores
         ProfScope ps__(c, K_WEIGHTED_SUM, st, bytes, ops);
-        return launch_wsum_mfma(c, level, L1, xs, n_terms, w_res, c_out, acc, scratch, st);
+        return launch_wsum_mfma(c, level, L1, xs, xl, n_terms, w_res, c_out, acc, scratch, st);
     }
     dim3 grid((c->N + PW_THREADS - 1) / PW_THREADS, 2 * L1, (c_out + WS_OUT_TILE - 1) / WS_OUT_TILE);
     ProfScope ps__(c, K_WEIGHTED_SUM, st, bytes, ops);
-    hipLaunchKernelGGL(weighted_sum_kernel, grid, dim3(PW_THREADS), 0, st, xs, w_res, acc, c->d_mc, c->N, level, L1, c->num_q, n_terms,
+    hipLaunchKernelGGL(weighted_sum_kernel, grid, dim3(PW_THREADS), 0, st, xs, xl, w_res, acc, c->d_mc, c->N, level, L1, c->num_q, n_terms,
                        c_out, c->lazy_terms);
     return hipGetLastError();
 }

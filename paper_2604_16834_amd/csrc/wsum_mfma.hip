@@ -95,7 +95,7 @@ __device__ __forceinline__ void digits_to_b(const u64* v, uint4* bw) {
     for (u32 dx = 0; dx < 7; dx++) bw[dx] = make_uint4(w[dx][0], w[dx][1], w[dx][2], w[dx][3]);
 }
 
-// xs [n_terms][2][nl][N], wa as above, acc [c_out][2][nl][N];  grid = (ceil(N/64), 2*nl, OT/2).
+// xs: the n_terms operands in layout xl, wa as above, acc [c_out][2][nl][N];  grid = (ceil(N/64), 2*nl, OT/2).
 // RAGGED: n_terms is not a multiple of 64 or N is not a multiple of 64 (addresses are clamped and
 // the values behind them masked to zero); the regular case carries none of that.
 //
@@ -107,7 +107,7 @@ __device__ __forceinline__ void digits_to_b(const u64* v, uint4* bw) {
 // then run the 98 matrix instructions of block kb out of LDS while the vector ALU turns X of block
 // kb+1 (requested an iteration ago) into digits for the other LDS buffer.
 template <bool RAGGED>
-__global__ __launch_bounds__(WM_THREADS) void wsum_mfma_kernel(const u64* __restrict__ xs, const uint4* __restrict__ wa,
+__global__ __launch_bounds__(WM_THREADS) void wsum_mfma_kernel(const u64* __restrict__ xs, XLayout xl, const uint4* __restrict__ wa,
                                                                u64* __restrict__ acc, const ModConst* __restrict__ mc, u32 N,
                                                                u32 level, u32 nl, u32 num_q, u32 n_terms, u32 c_out, u32 KB, u32 OT) {
     __shared__ uint4 lds_a[2][WM_A_STAGE];
@@ -131,8 +131,9 @@ __global__ __launch_bounds__(WM_THREADS) void wsum_mfma_kernel(const u64* __rest
         for (int r = 0; r < 16; r++) d[s][r] = 0;
 
     // term 64*kb + 32*wt + j + 16*g of column x: a wave-uniform row pointer plus a 32-bit lane offset
-    const u64* xbase = xs + ((size_t)comp * nl + e) * N + (size_t)(32 * wt) * ct_stride;
-    const u32 lane_off = (u32)(16 * g * ct_stride) + (x_ok ? x : N - 1);
+    const u32 xc = x_ok ? x : N - 1;
+    const u64* xbase = xs + comp * xl.s_comp + e * xl.s_e + (size_t)(32 * wt) * xl.s_k;
+    const u32 lane_off = (u32)(16 * g * xl.s_k + (size_t)(xc >> 6) * xl.s_xt + (xc & 63));
     const uint4* wsrc = wa + ((size_t)e * KB * OT + ot0) * (WM_DIGITS * 2 * 64) + tid;  // block kb: + kb * wstep
     const size_t wstep = (size_t)OT * (WM_DIGITS * 2 * 64);
     u64 raw0[16], raw1[16];
@@ -141,9 +142,9 @@ __global__ __launch_bounds__(WM_THREADS) void wsum_mfma_kernel(const u64* __rest
     _Pragma("unroll") for (u32 j = 0; j < 16; j++) {                                                  \
         if (RAGGED) {                                                                                 \
             const u32 k = 64 * (KBLK) + 32 * wt + 16 * g + j;                                         \
-            RAW[j] = xs[(size_t)(k < n_terms ? k : n_terms - 1) * ct_stride + ((size_t)comp * nl + e) * N + (x_ok ? x : N - 1)]; \
+            RAW[j] = xs[xl.at(k < n_terms ? k : n_terms - 1, comp, e, xc)];                             \
         } else {                                                                                      \
-            RAW[j] = (xbase + (size_t)(64 * (KBLK) + j) * ct_stride)[lane_off];                       \
+            RAW[j] = (xbase + (size_t)(64 * (KBLK) + j) * xl.s_k)[lane_off];                          \
         }                                                                                             \
     }
 #define WM_MASK_X(RAW, KBLK)                                                                          \
@@ -259,20 +260,20 @@ size_t wsum_mfma_scratch_elems(u32 n_limbs, u32 n_terms, u32 c_out) {
     return (size_t)n_limbs * KB * OT * WM_DIGITS * 2 * 64 * 2;  // 16 bytes per lane
 }
 
-hipError_t launch_wsum_mfma(const ckks_ctx* c, u32 level, u32 nl, const u64* xs, u32 n_terms, const u64* w_res, u32 c_out, u64* acc,
-                            u64* scratch, hipStream_t st) {
+hipError_t launch_wsum_mfma(const ckks_ctx* c, u32 level, u32 nl, const u64* xs, XLayout xl, u32 n_terms, const u64* w_res, u32 c_out,
+                            u64* acc, u64* scratch, hipStream_t st) {
     const u32 KB = (n_terms + 63) / 64, OT = (c_out + 63) / 64 * WM_OT_PER_WG;
     const size_t prep = (size_t)nl * KB * OT * WM_DIGITS * 2 * 64;
     hipLaunchKernelGGL(wsum_prep_kernel, dim3((u32)((prep + WM_THREADS - 1) / WM_THREADS)), dim3(WM_THREADS), 0, st, w_res,
                        (uint4*)scratch, c_out, n_terms, nl, KB, OT);
     dim3 grid((c->N + 63) / 64, 2 * nl, OT / WM_OT_PER_WG);
     // the 32-bit lane offset of the regular kernel spans 16 terms: 16 * (2 * nl * N) words must fit
-    const bool ragged = (n_terms & 63) || (c->N & 63) || (size_t)16 * 2 * nl * c->N + c->N > 0xffffffffull;
+    const bool ragged = (n_terms & 63) || (c->N & 63) || 16 * xl.s_k + (size_t)(c->N >> 6) * xl.s_xt + 64 > 0xffffffffull;
     if (ragged)
-        hipLaunchKernelGGL(wsum_mfma_kernel<true>, grid, dim3(WM_THREADS), 0, st, xs, (const uint4*)scratch, acc, c->d_mc, c->N, level,
+        hipLaunchKernelGGL(wsum_mfma_kernel<true>, grid, dim3(WM_THREADS), 0, st, xs, xl, (const uint4*)scratch, acc, c->d_mc, c->N, level,
                            nl, c->num_q, n_terms, c_out, KB, OT);
     else
-        hipLaunchKernelGGL(wsum_mfma_kernel<false>, grid, dim3(WM_THREADS), 0, st, xs, (const uint4*)scratch, acc, c->d_mc, c->N, level,
+        hipLaunchKernelGGL(wsum_mfma_kernel<false>, grid, dim3(WM_THREADS), 0, st, xs, xl, (const uint4*)scratch, acc, c->d_mc, c->N, level,
                            nl, c->num_q, n_terms, c_out, KB, OT);
     return hipGetLastError();
 }
