@@ -65,6 +65,7 @@ extern "C" void ckks_ctx_destroy(ckks_ctx* c) {
     (void)hipFree(c->d_twf);
     (void)hipFree(c->d_itwf);
     (void)hipFree(c->d_mcf);
+    (void)hipFree(c->d_pow256);
     (void)hipFree(c->d_modup);
     (void)hipFree(c->d_moddown);
     (void)hipFree(c->d_moddown_rs);
@@ -158,6 +159,20 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
         }
     }
 
+    // powers of 256 modulo every modulus, in 25-bit halves: the matrix-core multiply-accumulate folds its 13 digit
+    // diagonals with them
+    std::vector<u32> pow256;
+    if (c->small_q) {
+        pow256.resize((size_t)M * 26);
+        for (u32 t = 0; t < M; t++) {
+            u64 v = 1 % c->mod[t];
+            for (u32 s = 0; s < 13; s++) {
+                pow256[(size_t)t * 26 + 2 * s] = (u32)(v & 0x1ffffffu);
+                pow256[(size_t)t * 26 + 2 * s + 1] = (u32)(v >> 25);
+                v = h_mulmod(v, 256, c->mod[t]);
+            }
+        }
+    }
     // ModUp tables, one per (level, digit): the digit modulus is the product of the digit's LIVE limbs
     std::vector<u64> modup;
     if (c->dnum) {
@@ -268,6 +283,7 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
     if (e == hipSuccess) e = upload(twf, &c->d_twf);
     if (e == hipSuccess) e = upload(itwf, &c->d_itwf);
     if (e == hipSuccess) e = upload(mcf, &c->d_mcf);
+    if (e == hipSuccess) e = upload(pow256, &c->d_pow256);
     if (e == hipSuccess) e = upload(modup, &c->d_modup);
     if (e == hipSuccess) e = upload(moddown, &c->d_moddown);
     if (e == hipSuccess) e = upload(moddown_rs, &c->d_moddown_rs);

@@ -108,6 +108,7 @@ struct ckks_ctx {
     TwF* d_twf = nullptr;             // [M][N]  psi^bitrev(i) and psi^bitrev(i) / q as doubles
     TwF* d_itwf = nullptr;
     ModConstF* d_mcf = nullptr;       // [M]
+    u32* d_pow256 = nullptr;          // [M][13][2]: 2^(8s) mod q split into its low 25 bits and the rest (moduli below 2^50 only)
     u64* d_modup = nullptr;           // per level, per digit: see modup_digit_stride()
     u64* d_moddown = nullptr;         // phat_inv[k_pad], phat_inv_sh[k_pad], phat_q[num_q][k_pad], pinv[num_q], pinv_sh[num_q], negp[num_q]
     u64* d_moddown_rs = nullptr;      // per level l >= 1, the same layout (k_pad -> k2_pad) for the dropped set {q_l, p_0..p_{k-1}}:

@@ -108,8 +108,9 @@ __device__ __forceinline__ void digits_to_b(const u64* v, uint4* bw) {
 // kb+1 (requested an iteration ago) into digits for the other LDS buffer.
 template <bool RAGGED>
 __global__ __launch_bounds__(WM_THREADS) void wsum_mfma_kernel(const u64* __restrict__ xs, XLayout xl, const uint4* __restrict__ wa,
-                                                               u64* __restrict__ acc, const ModConst* __restrict__ mc, u32 N,
-                                                               u32 level, u32 nl, u32 num_q, u32 n_terms, u32 c_out, u32 KB, u32 OT) {
+                                                               u64* __restrict__ acc, const ModConst* __restrict__ mc,
+                                                               const u32* __restrict__ pow256, u32 N, u32 level, u32 nl, u32 num_q,
+                                                               u32 n_terms, u32 c_out, u32 KB, u32 OT) {
     __shared__ uint4 lds_a[2][WM_A_STAGE];
     __shared__ uint4 lds_b[2][WM_A_STAGE];  // [column tile 2][32-term step 2][digit 7][lane 64]
     const u32 tid = threadIdx.x, lane = tid & 63;
@@ -229,26 +230,37 @@ __global__ __launch_bounds__(WM_THREADS) void wsum_mfma_kernel(const u64* __rest
 #undef WM_A_LD
 #undef WM_A_ST
 
-    // sum_s D_s 2^(8s): the exact, non-negative sum of products (below n_terms * 2^100), reduced once
+    // sum_s D_s 2^(8s) is the exact sum of products; modulo q it equals sum_s D_s c_s with c_s = 2^(8s) mod q.
+    // c_s comes in 25-bit halves, so the two signed sums of 13 products (27 x 25 bits each) fit 64 bits, and
+    // V = S_lo + 2^25 S_hi (below 2^82 in magnitude) takes one Barrett reduction.
     if (!x_ok) return;
-    const ModConst m = mc[e <= level ? e : num_q + (e - level - 1)];
+    const u32 mi = e <= level ? e : num_q + (e - level - 1);
+    const ModConst m = mc[mi];
+    const u32* __restrict__ pw = pow256 + (size_t)mi * 26;
+    u32 clo[WM_DIAGS], chi[WM_DIAGS];
+#pragma unroll
+    for (u32 s = 0; s < WM_DIAGS; s++) {
+        clo[s] = pw[2 * s];
+        chi[s] = pw[2 * s + 1];
+    }
 #pragma unroll
     for (u32 r = 0; r < 16; r++) {
         const u32 o = 32 * (ot0 + wt) + 8 * (r >> 2) + 4 * g + (r & 3);
         if (o >= c_out) continue;
-        // three diagonals per 64-bit word, then Horner in 128 bits with steps of 24 bits
-        long long T[5];
+        long long slo = 0, shi = 0;
 #pragma unroll
-        for (u32 j = 0; j < 4; j++)
-            T[j] = (long long)d[3 * j][r] + (long long)d[3 * j + 1][r] * 256 + (long long)d[3 * j + 2][r] * 65536;
-        T[4] = (long long)d[12][r];
-        __int128 val = T[4];
-#pragma unroll
-        for (int j = 3; j >= 0; j--) val = val * (1 << 24) + T[j];
+        for (u32 s = 0; s < WM_DIAGS; s++) {
+            slo += (long long)d[s][r] * (long long)(int)clo[s];
+            shi += (long long)d[s][r] * (long long)(int)chi[s];
+        }
+        __int128 val = (__int128)shi * (1 << 25) + slo;
+        const bool neg = val < 0;
+        if (neg) val = -val;
         U128 u;
         u.lo = (u64)val;
         u.hi = (u64)(val >> 64);
-        acc[(size_t)o * ct_stride + off] = barrett_reduce(u, m);
+        const u64 rr = barrett_reduce(u, m);
+        acc[(size_t)o * ct_stride + off] = (neg && rr) ? m.q - rr : rr;
     }
 }
 
@@ -270,10 +282,10 @@ hipError_t launch_wsum_mfma(const ckks_ctx* c, u32 level, u32 nl, const u64* xs,
     // the 32-bit lane offset of the regular kernel spans 16 terms: 16 * (2 * nl * N) words must fit
     const bool ragged = (n_terms & 63) || (c->N & 63) || 16 * xl.s_k + (size_t)(c->N >> 6) * xl.s_xt + 64 > 0xffffffffull;
     if (ragged)
-        hipLaunchKernelGGL(wsum_mfma_kernel<true>, grid, dim3(WM_THREADS), 0, st, xs, xl, (const uint4*)scratch, acc, c->d_mc, c->N, level,
-                           nl, c->num_q, n_terms, c_out, KB, OT);
+        hipLaunchKernelGGL(wsum_mfma_kernel<true>, grid, dim3(WM_THREADS), 0, st, xs, xl, (const uint4*)scratch, acc, c->d_mc, c->d_pow256, c->N,
+                           level, nl, c->num_q, n_terms, c_out, KB, OT);
     else
-        hipLaunchKernelGGL(wsum_mfma_kernel<false>, grid, dim3(WM_THREADS), 0, st, xs, xl, (const uint4*)scratch, acc, c->d_mc, c->N, level,
-                           nl, c->num_q, n_terms, c_out, KB, OT);
+        hipLaunchKernelGGL(wsum_mfma_kernel<false>, grid, dim3(WM_THREADS), 0, st, xs, xl, (const uint4*)scratch, acc, c->d_mc, c->d_pow256, c->N,
+                           level, nl, c->num_q, n_terms, c_out, KB, OT);
     return hipGetLastError();
 }
