@@ -641,6 +641,87 @@ class Oracle:
                      self.scalar_mul(self.drop_to_level(x3, l3), self.scalar_residues(k3, l3), l3), l3)
         return self.ctct_mul_relin_rescale(self.drop_to_level(x4, l3), B, rlk, l3, addend=A)     # level-4
 
+    # ------------------------------------------------------------------ fully connected layer
+    @staticmethod
+    def fc_shifts(d_in: int, d_out: int, batch: int, base: int):
+        """Offsets of the layout rotations: block j moves left by j*(d_in - d_out) = base_idx + mod_idx with
+        mod_idx = (j % base) * delta and base_idx = (j // base) * base * delta (the two-key decomposition)."""
+        delta = d_in - d_out
+        lo = [jl * delta for jl in range(min(base, batch))]
+        hi = [jh * base * delta for jh in range(-(-batch // base))]
+        return delta, lo, hi
+
+    def fc_operands(self, W: np.ndarray, bias: np.ndarray, batch: int, level: int, base: int, scale: float):
+        """Plaintext operands of the batched FC layer for an input at (level, scale):
+        w_enc [d_out][level+1][N]   row i of W replicated over the batch blocks, at scale q_level;
+        merge_mask [level][N]       ones at the slots j*d_in (where the inner sums land), at scale q_{level-1};
+        place_masks [batch][level-1][N]  block j's d_out slots after its first layout rotation, at scale q_{level-2};
+        bias_pt [level-2][N]        the bias replicated at stride d_out, at the ciphertext's scale."""
+        d_out, d_in = W.shape
+        q = self.moduli
+        delta, lo, hi = self.fc_shifts(d_in, d_out, batch, base)
+        w_enc = []
+        for i in range(d_out):
+            z = np.zeros(self.n)
+            z[:batch * d_in] = np.tile(W[i], batch)
+            w_enc.append(self.encode_ntt(z, float(q[level]), level))
+        z = np.zeros(self.n)
+        z[np.arange(batch) * d_in] = 1.0
+        merge_mask = self.encode_ntt(z, float(q[level - 1]), level - 1)
+        place = []
+        for j in range(batch):
+            z = np.zeros(self.n)
+            start = j * d_in - lo[j % base]
+            z[start:start + d_out] = 1.0
+            place.append(self.encode_ntt(z, float(q[level - 2]), level - 2))
+        z = np.zeros(self.n)
+        z[:batch * d_out] = np.tile(bias, batch)
+        bias_pt = self.encode_ntt(z, scale, level - 3)
+        return np.stack(w_enc), merge_mask, np.stack(place), bias_pt
+
+    def fc_batched(self, ct, level: int, d_in: int, d_out: int, batch: int, base: int, w_enc, merge_mask, place_masks, bias_pt,
+                   keys: Dict[int, np.ndarray]) -> np.ndarray:
+        """Batched fully connected layer ("Fully Connected Layer": FC evaluation and output reconstruction).
+        Input: block j of d_in slots holds x^(j); output (level-3): block j of d_out slots holds W x^(j) + bias.
+          1. C_i = Rescale(C_in (.) w_i^enc);  S_i = Sum_{d_in}(C_i) by log2(d_in) steps T <- T + Rot(T, 2^s):
+             slot j*d_in of S_i is the inner product of output i for batch element j (all j at once);
+          2. Merge: U = Rescale( sum_i Rot(S_i (.) E, -i) ): element (j, i) at slot j*d_in + i, zeros elsewhere;
+          3. layout: block j moves left by j*(d_in-d_out) in two rotations (mod_idx, then base_idx):
+             R_l = Rot(U, l*delta) for l < base (one shared decomposition);
+             V_h = Rescale( sum_l R_l (.) E'_{h*base+l} );   out = sum_h Rot(V_h, h*base*delta);
+          4. out += bias^enc.
+        keys maps every offset used (2^s; -i; l*delta; h*base*delta) to its rotation key."""
+        ct = _u64(ct)
+        assert d_in & (d_in - 1) == 0 and d_out <= d_in and batch * d_in <= self.n
+        delta, lo, hi = self.fc_shifts(d_in, d_out, batch, base)
+        # 1. per-output products and inner sums
+        S = []
+        for i in range(d_out):
+            t = self.rescale(self.ptct_mac([w_enc[i]], [ct], level), level)
+            step = 1
+            while step < d_in:
+                t = self.add(t, self.rotate(t, level - 1, step, keys[step], True), level - 1)
+                step *= 2
+            S.append(t)
+        # 2. merge over the outputs
+        U = self.accumulator_merge(S, level - 1, 1, merge_mask, {-i: keys[-i] for i in range(1, d_out)})
+        # 3. layout
+        l2 = level - 2
+        digits = self.modup(U[1], l2)
+        R = [U if l == 0 else self.rotate(U, l2, lo[l], keys.get(lo[l]), True, digits) for l in range(len(lo))]
+        out = None
+        for h in range(len(hi)):
+            js = [h * base + l for l in range(len(lo)) if h * base + l < batch]
+            V = self.rescale(self.ptct_mac([place_masks[j] for j in js], [R[j % base] for j in js], l2), l2)
+            if h:
+                V = self.rotate(V, l2 - 1, hi[h], keys.get(hi[h]), True)
+            out = V if out is None else self.add(out, V, l2 - 1)
+        # 4. bias
+        out = out.copy()
+        for i in range(l2):
+            out[0, i] = (out[0, i] + bias_pt[i]) % np.uint64(self.moduli[i])
+        return out
+
     # ----------------------------------------------------------------------- activation
     def act_schedule(self, level: int, scale: float) -> dict:
         """Levels, scales and integer scalars of the degree-7 activation evaluated on a

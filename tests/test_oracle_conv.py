@@ -335,3 +335,30 @@ def test_he_conv_deferred_with_merged_division_decrypts_to_float_conv():
         z = o.decrypt(ct, level - 1, s_ntt, scale)
         assert np.abs(o.unpack_channel(z, wl.batch, wl.height, wl.width) - want[:, oc]).max() < 1e-4
         assert np.abs(z - o.decrypt(two[oc], level - 1, s_ntt, scale)).max() < 1e-6
+
+
+@pytest.mark.parametrize("d_in,d_out,batch,base", [(16, 4, 8, 3), (8, 8, 4, 2), (32, 10, 16, 4)])
+def test_fc_batched_decrypts_to_the_affine_map(d_in, d_out, batch, base):
+    """y = W x + b for every batch element, outputs packed at stride d_out (float64 reference: numpy matmul)."""
+    p = make_params(10, 6, 2, 3)
+    o = Oracle(p)
+    level = p.num_q - 1
+    s, s_ntt = o.gen_secret(13000)
+    rng = np.random.default_rng(9)
+    W = rng.normal(0, 0.3, (d_out, d_in))
+    bias = rng.uniform(-0.5, 0.5, d_out)
+    X = rng.uniform(-1, 1, (batch, d_in))
+    z = np.zeros(o.n)
+    z[:batch * d_in] = X.reshape(-1)
+    scale = 2.0 ** 40
+    ct = o.encrypt(z, scale, level, s_ntt, 13001)
+    delta, lo, hi = o.fc_shifts(d_in, d_out, batch, base)
+    offsets = {2 ** t for t in range(d_in.bit_length() - 1)} | {-i for i in range(1, d_out)} | set(lo[1:]) | set(hi[1:])
+    keys = {r: o.gen_rotation_key(s, s_ntt, r, 13100 + k) for k, r in enumerate(sorted(offsets)) if r % o.n}
+    ops = o.fc_operands(W, bias, batch, level, base, scale)
+    out = o.fc_batched(ct, level, d_in, d_out, batch, base, *ops, keys)
+    assert out.shape == (2, level - 2, o.N)
+    got = o.decrypt(out, level - 3, s_ntt, scale)
+    want = (X @ W.T + bias).reshape(-1)
+    assert np.abs(got[:batch * d_out] - want).max() < 1e-4
+    assert np.abs(got[batch * d_out:]).max() < 1e-4             # everything else is clean
