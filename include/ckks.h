@@ -195,6 +195,29 @@ int he_accumulator_merge(const ckks_ctx* ctx, const uint64_t* const* h_d_cts, ui
                          const uint64_t* d_mask, const ckks_key* const* keys, uint64_t* d_out, void* d_ws,
                          size_t ws_bytes, void* stream);
 
+/* Batched fully connected layer ("Fully Connected Layer": FC evaluation and output reconstruction).  The input
+ * ciphertext holds x^(j) (d_in values, d_in a power of two) in slots [j*d_in, (j+1)*d_in) for j < batch
+ * (batch*d_in <= N/2); the output, three levels lower, holds W x^(j) + bias in slots [j*d_out, (j+1)*d_out).
+ *   1. C_i = Rescale(C_in (.) w_i^enc), S_i = Sum_{d_in}(C_i) by log2(d_in) steps T <- T + Rot(T, 2^s)   (i < d_out)
+ *   2. U = Rescale( sum_i Rot(S_i (.) E, -i) )                  element (j, i) at slot j*d_in + i
+ *   3. R_l = Rot(U, l*delta), l < base, delta = d_in - d_out    (mod_idx rotations; one decomposition)
+ *      V_h = Rescale( sum_l R_l (.) E'_{h*base+l} );  out = sum_h Rot(V_h, h*base*delta)   (base_idx rotations)
+ *   4. out_0 += bias^enc
+ * Operands (all NTT form): d_w_enc uint64[d_out][level+1][N] (row i of W replicated over the batch blocks),
+ * d_merge_mask uint64[level][N] (ones at slots j*d_in), d_place_masks uint64[batch][level-1][N] (block j's d_out
+ * slots after its first rotation: ones at [j*d_in - (j % base)*delta, +d_out)), d_bias uint64[level-2][N].
+ * Keys: sum_keys[s] for offset 2^s (s < log2 d_in), merge_keys[i] for -i, lo_keys[l] for l*delta, hi_keys[h] for
+ * h*base*delta (entries whose offset is 0 mod N/2 are ignored).  base = 0 means ceil(sqrt(batch)).
+ * d_in_ct uint64[2][level+1][N], level >= 3; d_out uint64[2][level-2][N]; d_out <= 16 outputs per call. */
+typedef struct he_fc_desc {
+    uint32_t d_in, d_out, batch, level, base;
+} he_fc_desc;
+size_t he_fc_workspace_bytes(const ckks_ctx* ctx, const he_fc_desc* desc);
+int he_fc_batched(const ckks_ctx* ctx, const he_fc_desc* desc, const uint64_t* d_in_ct, const uint64_t* d_w_enc,
+                  const ckks_key* const* sum_keys, const ckks_key* const* merge_keys, const uint64_t* d_merge_mask,
+                  const uint64_t* d_place_masks, const ckks_key* const* lo_keys, const ckks_key* const* hi_keys,
+                  const uint64_t* d_bias, uint64_t* d_out, void* d_ws, size_t ws_bytes, void* stream);
+
 /* Odd degree-7 polynomial activation on a vector of n_ct channel ciphertexts, four ciphertext
  * products each ("Other Layers": the activation applied independently to every element of the
  * channel vector):  x2 = x*x, x3 = x2*x, x4 = x2*x2 (each rescaled once),

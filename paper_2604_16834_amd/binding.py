@@ -42,7 +42,7 @@ EXPORTS = (
     "ckks_ntt_fwd", "ckks_ntt_inv", "ckks_key_load", "ckks_key_free", "ckks_galois_element",
     "ckks_keyswitch", "ckks_rotate_hoisted", "ckks_ptct_mac", "ckks_rescale", "ckks_ctct_mul_relin",
     "he_conv_workspace_bytes", "he_conv_batched", "he_poly_act_deg7",
-    "he_accumulator_workspace_bytes", "he_accumulator_merge",
+    "he_accumulator_workspace_bytes", "he_accumulator_merge", "he_fc_workspace_bytes", "he_fc_batched",
     "ckks_prof_kernel_count", "ckks_prof_kernel_name", "ckks_prof_begin", "ckks_prof_end",
 )
 
@@ -63,6 +63,10 @@ class _Params(C.Structure):
 class _ConvDesc(C.Structure):
     _fields_ = [("c_in", C.c_uint32), ("c_out", C.c_uint32), ("height", C.c_uint32), ("width", C.c_uint32),
                 ("batch", C.c_uint32), ("level", C.c_uint32), ("alignment", C.c_uint32)]
+
+
+class _FcDesc(C.Structure):
+    _fields_ = [("d_in", C.c_uint32), ("d_out", C.c_uint32), ("batch", C.c_uint32), ("level", C.c_uint32), ("base", C.c_uint32)]
 
 
 def _bind(path: str):
@@ -96,6 +100,10 @@ def _bind(path: str):
     lib.he_accumulator_workspace_bytes.argtypes = [vp, u32, u32]
     lib.he_accumulator_workspace_bytes.restype = sz
     lib.he_accumulator_merge.argtypes = [vp, C.POINTER(vp), u32, u32, u32, vp, C.POINTER(vp), vp, vp, sz, vp]
+    lib.he_fc_workspace_bytes.argtypes = [vp, C.POINTER(_FcDesc)]
+    lib.he_fc_workspace_bytes.restype = sz
+    lib.he_fc_batched.argtypes = [vp, C.POINTER(_FcDesc), vp, vp, C.POINTER(vp), C.POINTER(vp), vp, vp, C.POINTER(vp), C.POINTER(vp),
+                                  vp, vp, vp, sz, vp]
     lib.ckks_prof_kernel_count.restype = u32
     lib.ckks_prof_kernel_name.argtypes = [u32]
     lib.ckks_prof_kernel_name.restype = C.c_char_p
@@ -394,6 +402,42 @@ def he_accumulator_merge(ctx: Context, cts: Sequence[torch.Tensor], level: int, 
     ka = _ptr_array([k.handle.value if k is not None else None for k in keys])
     ctx._check(_lib.he_accumulator_merge(ctx.handle, ca, g, level, sts, _ptr(mask), ka, _ptr(out), _ptr(ws),
                                          ws.numel() * ws.element_size(), _stream(stream)))
+    return out
+
+
+def he_fc_workspace_bytes(ctx: Context, d_in: int, d_out: int, batch: int, level: int, base: int = 0) -> int:
+    return int(_lib.he_fc_workspace_bytes(ctx.handle, C.byref(_FcDesc(d_in, d_out, batch, level, base))))
+
+
+def he_fc_batched(ctx: Context, ct: torch.Tensor, level: int, d_in: int, d_out: int, batch: int, base: int, w_enc: torch.Tensor,
+                  merge_mask: torch.Tensor, place_masks: torch.Tensor, bias: torch.Tensor, sum_keys: Sequence[Key],
+                  merge_keys: Sequence[Optional[Key]], lo_keys: Sequence[Optional[Key]], hi_keys: Sequence[Optional[Key]],
+                  out: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """ct [2][level+1][N] with x^(j) in slots [j*d_in, (j+1)*d_in); w_enc [d_out][level+1][N]; merge_mask [level][N];
+    place_masks [batch][level-1][N]; bias [level-2][N].  sum_keys[s]: offset 2^s; merge_keys[i]: offset -i;
+    lo_keys[l]: offset l*(d_in-d_out); hi_keys[h]: offset h*base*(d_in-d_out) (entries of offset 0 may be None).
+    Returns [2][level-2][N] with W x^(j) + bias in slots [j*d_out, (j+1)*d_out)."""
+    N = ctx.N
+    if level < 3:
+        raise ValueError("the layer needs level >= 3")
+    n_base = base if base else next(b for b in range(1, batch + 1) if b * b >= batch)
+    want = dict(ct=(ct, 2 * (level + 1) * N), w_enc=(w_enc, d_out * (level + 1) * N), merge_mask=(merge_mask, level * N),
+                place_masks=(place_masks, batch * (level - 1) * N), bias=(bias, (level - 2) * N))
+    for name, (t, n) in want.items():
+        if t.numel() != n:
+            raise ValueError(f"{name} has {t.numel()} elements, expected {n}")
+    if len(sum_keys) != d_in.bit_length() - 1 or len(merge_keys) != d_out or len(lo_keys) != min(n_base, batch) \
+            or len(hi_keys) != -(-batch // n_base):
+        raise ValueError("key lists do not match the layer's rotations")
+    if out is None:
+        out = empty(2, level - 2, N)
+    if out.numel() != 2 * (level - 2) * N:
+        raise ValueError("out must be [2][level-2][N]")
+    ws = _ws(ctx, ws, he_fc_workspace_bytes(ctx, d_in, d_out, batch, level, base))
+    arr = lambda ks: _ptr_array([k.handle.value if k is not None else None for k in ks])
+    ctx._check(_lib.he_fc_batched(ctx.handle, C.byref(_FcDesc(d_in, d_out, batch, level, base)), _ptr(ct), _ptr(w_enc), arr(sum_keys),
+                                  arr(merge_keys), _ptr(merge_mask), _ptr(place_masks), arr(lo_keys), arr(hi_keys), _ptr(bias),
+                                  _ptr(out), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)))
     return out
 
 

@@ -7,6 +7,7 @@
 // the chip); the rotations of one ciphertext share its extended digits (hoisting).
 #include <cstdio>
 #include <new>
+#include <vector>
 
 #include "ctx.h"
 
@@ -293,6 +294,67 @@ int conv_deferred(const ckks_ctx* c, const he_conv_desc* d, const u32* gs, const
     }
     return CKKS_OK;
 }
+
+// n <= CT_BATCH different ciphertexts srcs[b] ([2][level+1][N]) rotated, outs[b] = Rot(srcs[b]) ([2][level+1][N], no overlap).
+// key_of(b) / gal[b]: one key for all (shared: the key streams once for the batch) or one per item.
+int run_rotate_batch(const ckks_ctx* c, u32 level, u32 n, const u64* const* srcs, const ckks_key* const* keys, bool shared_key,
+                     const u32* gal, u64* const* outs, const KsWs& ws, hipStream_t st) {
+    const size_t N = c->N, L1 = level + 1;
+    const u64* c1s[CT_BATCH];
+    FinalItem items[CT_BATCH];
+    for (u32 b = 0; b < n; b++) c1s[b] = srcs[b] + L1 * N;
+    int rc = run_modup(c, level, c1s, n, ws, st);
+    if (rc) return rc;
+    if (shared_key) {
+        HIP_TRY(launch_key_inner_multi(c, level, ws.digits, ws.dig_b, keys[0]->d_key, gal[0], ws.v, ws.v_b, n, st));
+    } else {
+        for (u32 b = 0; b < n; b++)
+            HIP_TRY(launch_key_inner(c, level, ws.digits + b * ws.dig_b, keys[b]->d_key, gal[b], ws.v + b * ws.v_b, st));
+    }
+    for (u32 b = 0; b < n; b++) items[b] = FinalItem{srcs[b], nullptr, nullptr, outs[b], gal[shared_key ? 0 : b], 0};
+    return run_moddown(c, level, ws, n, items, st);
+}
+
+size_t ws_merge(const ckks_ctx* c, u32 level, u32 g) {
+    const size_t N = c->N, L1 = level + 1;
+    const u32 nb = g - 1 < CT_BATCH ? (g > 1 ? g - 1 : 1) : CT_BATCH;
+    return ws_ks(c, level, nb, nb) + 2 * blk((size_t)g * 2 * L1 * N) + blk(2 * L1 * N) + ws_rescale(c, level, 1);
+}
+
+// out = Rescale( sum_{i<g} Rot(cts[i] (.) mask, -i*sts) ), g <= KS_MAX_BATCH; keys[i] / gal[i] for i >= 1 (validated by the caller)
+int run_merge(const ckks_ctx* c, const u64* const* cts, u32 g, u32 level, const u64* mask, const ckks_key* const* keys, const u32* gal,
+              u64* out, Arena ar, hipStream_t st) {
+    const size_t N = c->N, L1 = level + 1, ct_elems = 2 * L1 * N;
+    const u32 nb = g - 1 < CT_BATCH ? (g > 1 ? g - 1 : 1) : CT_BATCH;
+    KsWs ws;
+    bool ok = carve_ks(c, level, nb, nb, ar, ws);
+    u64* masked = ar.take((size_t)g * ct_elems);   // C_i (.) M
+    u64* rotated = ar.take((size_t)g * ct_elems);  // Rot(C_i (.) M, -i*sts), i >= 1
+    u64* total = ar.take(ct_elems);
+    if (!ok || !ar.ok() || ar.used + ws_rescale(c, level, 1) > ar.cap)
+        return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for the merge");
+    for (u32 i = 0; i < g; i++) HIP_TRY(launch_mask_mul(c, level, mask, cts[i], masked + i * ct_elems, st));
+    // blocks 1..g-1: every block has its own key; a batch shares the decomposition and ModDown launches
+    for (u32 i0 = 1; i0 < g; i0 += nb) {
+        const u32 n = g - i0 < nb ? g - i0 : nb;
+        const u64* srcs[CT_BATCH];
+        u64* outs[CT_BATCH];
+        for (u32 b = 0; b < n; b++) {
+            srcs[b] = masked + (i0 + b) * ct_elems;
+            outs[b] = rotated + (i0 + b) * ct_elems;
+        }
+        int rc = run_rotate_batch(c, level, n, srcs, keys + i0, false, gal + i0, outs, ws, st);
+        if (rc) return rc;
+    }
+    const u64* terms[KS_MAX_BATCH];
+    terms[0] = masked;
+    for (u32 i = 1; i < g; i++) terms[i] = rotated + i * ct_elems;
+    HIP_TRY(launch_ct_sum(c, level, ptr_list(terms, g), g, total, st));
+    const u64* in = total;
+    return run_rescale(c, level, &in, L1 * N, &out, 1, ar.rest(), st);
+}
+
+u32 ilog2(u32 v) { u32 r = 0; while ((1u << (r + 1)) <= v) r++; return r; }
 
 }  // namespace
 
@@ -647,9 +709,7 @@ int he_conv_batched(const ckks_ctx* c, const he_conv_desc* d, const uint64_t* co
 
 size_t he_accumulator_workspace_bytes(const ckks_ctx* c, uint32_t level, uint32_t g) {
     if (!c || !c->dnum || !level_ok(c, level) || level < 1 || g == 0 || g > KS_MAX_BATCH) return 0;
-    const size_t N = c->N, L1 = level + 1;
-    const u32 nb = g - 1 < CT_BATCH ? (g > 1 ? g - 1 : 1) : CT_BATCH;
-    return ws_ks(c, level, nb, nb) + 2 * blk((size_t)g * 2 * L1 * N) + blk(2 * L1 * N) + ws_rescale(c, level, 1);
+    return ws_merge(c, level, g);
 }
 
 int he_accumulator_merge(const ckks_ctx* c, const uint64_t* const* h_d_cts, uint32_t g, uint32_t level, uint32_t sts,
@@ -669,40 +729,193 @@ int he_accumulator_merge(const ckks_ctx* c, const uint64_t* const* h_d_cts, uint
         if (!keys || !keys[i]) return set_err(c, CKKS_ERR_NO_KEY, "rotation key missing for a block");
         if (keys[i]->galois_elt != gal[i]) return set_err(c, CKKS_ERR_NO_KEY, "rotation key does not match the block's offset");
     }
-    const size_t N = c->N, L1 = level + 1, ct_elems = 2 * L1 * N;
-    const u32 nb = g - 1 < CT_BATCH ? (g > 1 ? g - 1 : 1) : CT_BATCH;
-    Arena ar(d_ws, ws_bytes);
-    KsWs ws;
-    bool ok = carve_ks(c, level, nb, nb, ar, ws);
-    u64* masked = ar.take((size_t)g * ct_elems);   // C_i (.) M
-    u64* rotated = ar.take((size_t)g * ct_elems);  // Rot(C_i (.) M, -i*sts), i >= 1
-    u64* total = ar.take(ct_elems);
-    if (!ok || !ar.ok() || ar.used + ws_rescale(c, level, 1) > ar.cap)
-        return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for the merge");
-    hipStream_t st = (hipStream_t)stream;
-    for (u32 i = 0; i < g; i++)
-        HIP_TRY(launch_mask_mul(c, level, (const u64*)d_mask, (const u64*)h_d_cts[i], masked + i * ct_elems, st));
-    // blocks 1..g-1: every block has its own key; a batch shares the decomposition and ModDown launches
-    for (u32 i0 = 1; i0 < g; i0 += nb) {
-        const u32 n = g - i0 < nb ? g - i0 : nb;
-        const u64* c1s[CT_BATCH];
-        FinalItem items[CT_BATCH];
-        for (u32 b = 0; b < n; b++) c1s[b] = masked + (i0 + b) * ct_elems + L1 * N;
-        int rc = run_modup(c, level, c1s, n, ws, st);
-        if (rc) return rc;
-        for (u32 b = 0; b < n; b++) {
-            HIP_TRY(launch_key_inner(c, level, ws.digits + b * ws.dig_b, keys[i0 + b]->d_key, gal[i0 + b], ws.v + b * ws.v_b, st));
-            items[b] = FinalItem{masked + (i0 + b) * ct_elems, nullptr, nullptr, rotated + (i0 + b) * ct_elems, gal[i0 + b], 0};
-        }
-        if ((rc = run_moddown(c, level, ws, n, items, st))) return rc;
+    return run_merge(c, (const u64* const*)h_d_cts, g, level, (const u64*)d_mask, keys, gal, (u64*)d_out, Arena(d_ws, ws_bytes),
+                     (hipStream_t)stream);
+}
+
+// ---- batched fully connected layer ------------------------------------------------------------------
+static u32 fc_base(const he_fc_desc* d) {
+    if (d->base) return d->base;
+    u32 b = 1;
+    while (b * b < d->batch) b++;
+    return b;
+}
+
+size_t he_fc_workspace_bytes(const ckks_ctx* c, const he_fc_desc* d) {
+    if (!c || !d || !c->dnum || !level_ok(c, d->level) || d->level < 3 || d->d_out == 0 || d->d_out > KS_MAX_BATCH || d->batch == 0) return 0;
+    const size_t N = c->N;
+    const u32 level = d->level, base = fc_base(d), n_lo = base < d->batch ? base : d->batch, n_hi = (d->batch + base - 1) / base;
+    const size_t ct0 = 2 * (size_t)(level + 1) * N, ct1 = 2 * (size_t)level * N, ct2 = 2 * (size_t)(level - 1) * N, ct3 = 2 * (size_t)(level - 2) * N;
+    return blk(CT_BATCH * ct0) + blk(d->d_out * ct1) + blk(CT_BATCH * ct1) + blk(ct2) + blk(n_lo * ct2) + blk(n_hi * ct2) +
+           2 * blk(n_hi * ct3) + ws_ks(c, level - 1, CT_BATCH, CT_BATCH) + ws_merge(c, level - 1, d->d_out) + ws_rescale(c, level, CT_BATCH);
+}
+
+int he_fc_batched(const ckks_ctx* c, const he_fc_desc* d, const uint64_t* d_in, const uint64_t* d_w_enc, const ckks_key* const* sum_keys,
+                  const ckks_key* const* merge_keys, const uint64_t* d_merge_mask, const uint64_t* d_place_masks,
+                  const ckks_key* const* lo_keys, const ckks_key* const* hi_keys, const uint64_t* d_bias, uint64_t* d_out, void* d_ws,
+                  size_t ws_bytes, void* stream) {
+    if (!c) return CKKS_ERR_INVALID_ARG;
+    if (!d || !d_in || !d_w_enc || !d_merge_mask || !d_place_masks || !d_bias || !d_out) return set_err(c, CKKS_ERR_INVALID_ARG, "null pointer");
+    if (!c->dnum) return set_err(c, CKKS_ERR_UNSUPPORTED_PARAMS, "context has no key-switching digits");
+    if (!level_ok(c, d->level) || d->level < 3) return set_err(c, CKKS_ERR_LEVEL_MISMATCH, "the layer needs 3 <= level < num_q");
+    if (d->d_in == 0 || (d->d_in & (d->d_in - 1)) || d->d_out == 0 || d->d_out > d->d_in || d->batch == 0)
+        return set_err(c, CKKS_ERR_INVALID_ARG, "d_in must be a power of two and 1 <= d_out <= d_in");
+    if (d->d_out > KS_MAX_BATCH) return set_err(c, CKKS_ERR_UNSUPPORTED_PARAMS, "at most 16 outputs per call");
+    if ((u64)d->batch * d->d_in > c->N / 2) return set_err(c, CKKS_ERR_INVALID_ARG, "batch * d_in exceeds the N/2 slots");
+    const u32 level = d->level, l1 = level - 1, l2 = level - 2, l3 = level - 3;
+    const u32 base = fc_base(d), n_lo = base < d->batch ? base : d->batch, n_hi = (d->batch + base - 1) / base;
+    const u32 delta = d->d_in - d->d_out, n_sum = ilog2(d->d_in);
+    // Galois elements and keys of every rotation, checked before the first launch
+    u32 g_sum[32], g_merge[KS_MAX_BATCH];
+    for (u32 s = 0; s < n_sum; s++) {
+        g_sum[s] = ckks_galois_element(c, (int32_t)(1u << s));
+        if (!sum_keys || !sum_keys[s] || sum_keys[s]->galois_elt != g_sum[s]) return set_err(c, CKKS_ERR_NO_KEY, "key of an inner-sum rotation missing or wrong");
     }
-    const u64* terms[KS_MAX_BATCH];
-    terms[0] = masked;
-    for (u32 i = 1; i < g; i++) terms[i] = rotated + i * ct_elems;
-    HIP_TRY(launch_ct_sum(c, level, ptr_list(terms, g), g, total, st));
-    const u64* in = total;
+    for (u32 i = 0; i < d->d_out; i++) {
+        g_merge[i] = ckks_galois_element(c, -(int32_t)i);
+        if (i && (!merge_keys || !merge_keys[i] || merge_keys[i]->galois_elt != g_merge[i]))
+            return set_err(c, CKKS_ERR_NO_KEY, "key of a merge rotation missing or wrong");
+    }
+    std::vector<u32> g_lo(n_lo), g_hi(n_hi);
+    for (u32 l = 0; l < n_lo; l++) {
+        g_lo[l] = ckks_galois_element(c, (int32_t)(l * delta));
+        if (g_lo[l] != 1 && (!lo_keys || !lo_keys[l] || lo_keys[l]->galois_elt != g_lo[l]))
+            return set_err(c, CKKS_ERR_NO_KEY, "key of a layout rotation (mod_idx) missing or wrong");
+    }
+    for (u32 h = 0; h < n_hi; h++) {
+        g_hi[h] = ckks_galois_element(c, (int32_t)(h * base * delta));
+        if (g_hi[h] != 1 && (!hi_keys || !hi_keys[h] || hi_keys[h]->galois_elt != g_hi[h]))
+            return set_err(c, CKKS_ERR_NO_KEY, "key of a layout rotation (base_idx) missing or wrong");
+    }
+    const size_t N = c->N;
+    const size_t ct0 = 2 * (size_t)(level + 1) * N, ct1 = 2 * (size_t)(l1 + 1) * N, ct2 = 2 * (size_t)(l2 + 1) * N, ct3 = 2 * (size_t)(l3 + 1) * N;
+    Arena ar(d_ws, ws_bytes);
+    u64* prod = ar.take(CT_BATCH * ct0);        // C_in (.) w_i before its rescale
+    u64* S = ar.take(d->d_out * ct1);           // running inner sums, level-1
+    u64* Srot = ar.take(CT_BATCH * ct1);        // their rotations
+    u64* U = ar.take(ct2);                      // merged, level-2
+    u64* R = ar.take(n_lo * ct2);               // Rot(U, l*delta)
+    u64* Vacc = ar.take(n_hi * ct2);            // masked sums before their rescale
+    u64* V = ar.take(n_hi * ct3);               // level-3
+    u64* Vrot = ar.take(n_hi * ct3);
+    // one key-switch region, sized for the highest level used and carved again for each lower level
+    const size_t ks_bytes = ws_ks(c, l1, CT_BATCH, CT_BATCH);
+    u64* ks_region = ar.take(ks_bytes / sizeof(u64));
+    if (!ar.ok() || ar.used + ws_merge(c, l1, d->d_out) > ar.cap || ar.used + ws_rescale(c, level, CT_BATCH) > ar.cap)
+        return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for the layer");
+    KsWs ws;
+    auto ks_at = [&](u32 lv) {
+        Arena sub(ks_region, ks_bytes);
+        return carve_ks(c, lv, CT_BATCH, CT_BATCH, sub, ws);
+    };
+    if (!ks_at(l1)) return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for the layer");
+    hipStream_t st = (hipStream_t)stream;
+    const u64* in = (const u64*)d_in;
+    int rc;
+    // 1. per-output products, rescale, inner sums over d_in slots (all outputs of a batch share each rotation key)
+    for (u32 i0 = 0; i0 < d->d_out; i0 += CT_BATCH) {
+        const u32 n = d->d_out - i0 < CT_BATCH ? d->d_out - i0 : CT_BATCH;
+        const u64 *pp[CT_BATCH], *ps[CT_BATCH];
+        u64 *os[CT_BATCH], *orot[CT_BATCH];
+        for (u32 b = 0; b < n; b++) {
+            HIP_TRY(launch_mask_mul(c, level, (const u64*)d_w_enc + (size_t)(i0 + b) * (level + 1) * N, in, prod + b * ct0, st));
+            pp[b] = prod + b * ct0;
+            ps[b] = os[b] = S + (i0 + b) * ct1;
+            orot[b] = Srot + b * ct1;
+        }
+        if ((rc = run_rescale(c, level, pp, (size_t)(level + 1) * N, os, n, ar.rest(), st))) return rc;
+        for (u32 s = 0; s < n_sum; s++) {
+            const ckks_key* k = sum_keys[s];
+            if ((rc = run_rotate_batch(c, l1, n, ps, &k, true, &g_sum[s], orot, ws, st))) return rc;
+            for (u32 b = 0; b < n; b++) {
+                const u64* two[2] = {ps[b], orot[b]};
+                HIP_TRY(launch_ct_sum(c, l1, ptr_list(two, 2), 2, os[b], st));
+            }
+        }
+    }
+    // 2. merge over the outputs: element (j, i) to slot j*d_in + i
+    {
+        const u64* cts[KS_MAX_BATCH];
+        for (u32 i = 0; i < d->d_out; i++) cts[i] = S + i * ct1;
+        if ((rc = run_merge(c, cts, d->d_out, l1, (const u64*)d_merge_mask, merge_keys, g_merge, U, ar.rest(), st))) return rc;
+    }
+    // 3. layout.  First rotations (mod_idx = l*delta): hoisted, one decomposition of U
+    {
+        if (!ks_at(l2)) return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for the layer");
+        const u64* uc1 = U + (size_t)(l2 + 1) * N;
+        if ((rc = run_modup(c, l2, &uc1, 1, ws, st))) return rc;
+        HIP_TRY(launch_copy(U, R, ct2, st));
+        for (u32 l0 = 1; l0 < n_lo; l0 += CT_BATCH) {
+            const u32 n = n_lo - l0 < CT_BATCH ? n_lo - l0 : CT_BATCH;
+            FinalItem items[CT_BATCH];
+            u32 nk = 0;
+            for (u32 b = 0; b < n; b++) {
+                if (g_lo[l0 + b] == 1) {  // delta = 0: nothing moves
+                    HIP_TRY(launch_copy(U, R + (l0 + b) * ct2, ct2, st));
+                    continue;
+                }
+                HIP_TRY(launch_key_inner(c, l2, ws.digits, lo_keys[l0 + b]->d_key, g_lo[l0 + b], ws.v + nk * ws.v_b, st));
+                items[nk++] = FinalItem{U, nullptr, nullptr, R + (l0 + b) * ct2, g_lo[l0 + b], 0};
+            }
+            if (nk && (rc = run_moddown(c, l2, ws, nk, items, st))) return rc;
+        }
+    }
+    // masked sums per base block, rescaled
+    const size_t mask_elems = (size_t)(l2 + 1) * N;
+    for (u32 h = 0; h < n_hi; h++) {
+        std::vector<const u64*> pts, cts;
+        for (u32 l = 0; l < n_lo && h * base + l < d->batch; l++) {
+            pts.push_back((const u64*)d_place_masks + (size_t)(h * base + l) * mask_elems);
+            cts.push_back(R + l * ct2);
+        }
+        HIP_TRY(launch_ptct_mac(c, l2, pts.data(), cts.data(), (u32)pts.size(), Vacc + h * ct2, 0, st));
+    }
+    for (u32 h0 = 0; h0 < n_hi; h0 += CT_BATCH) {
+        const u32 n = n_hi - h0 < CT_BATCH ? n_hi - h0 : CT_BATCH;
+        const u64* pv[CT_BATCH];
+        u64* ov[CT_BATCH];
+        for (u32 b = 0; b < n; b++) {
+            pv[b] = Vacc + (h0 + b) * ct2;
+            ov[b] = V + (h0 + b) * ct3;
+        }
+        if ((rc = run_rescale(c, l2, pv, (size_t)(l2 + 1) * N, ov, n, ar.rest(), st))) return rc;
+    }
+    // second rotations (base_idx = h*base*delta), one key each, then the sum
+    if (!ks_at(l3)) return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for the layer");
+    for (u32 h0 = 1; h0 < n_hi; h0 += CT_BATCH) {
+        const u32 n = n_hi - h0 < CT_BATCH ? n_hi - h0 : CT_BATCH;
+        const u64* srcs[CT_BATCH];
+        const ckks_key* ks[CT_BATCH];
+        u32 gs[CT_BATCH];
+        u64* outs[CT_BATCH];
+        u32 nk = 0;
+        for (u32 b = 0; b < n; b++) {
+            if (g_hi[h0 + b] == 1) {
+                HIP_TRY(launch_copy(V + (h0 + b) * ct3, Vrot + (h0 + b) * ct3, ct3, st));
+                continue;
+            }
+            srcs[nk] = V + (h0 + b) * ct3;
+            ks[nk] = hi_keys[h0 + b];
+            gs[nk] = g_hi[h0 + b];
+            outs[nk++] = Vrot + (h0 + b) * ct3;
+        }
+        if (nk && (rc = run_rotate_batch(c, l3, nk, srcs, ks, false, gs, outs, ws, st))) return rc;
+    }
     u64* out = (u64*)d_out;
-    return run_rescale(c, level, &in, L1 * N, &out, 1, ar.rest(), st);
+    {
+        bool first = true;
+        for (u32 h0 = 0; h0 < n_hi; h0 += KS_MAX_BATCH - 1) {
+            const u64* terms[KS_MAX_BATCH];
+            u32 nt = 0;
+            if (!first) terms[nt++] = out;
+            for (u32 h = h0; h < n_hi && nt < KS_MAX_BATCH; h++) terms[nt++] = h == 0 ? V : Vrot + h * ct3;
+            HIP_TRY(launch_ct_sum(c, l3, ptr_list(terms, nt), nt, out, st));
+            first = false;
+        }
+    }
+    // 4. bias on component 0
+    HIP_TRY(launch_add_plain(c, l3, (const u64*)d_bias, out, st));
+    return CKKS_OK;
 }
 
 int he_poly_act_deg7(const ckks_ctx* c, const uint64_t* const* h_d_x, uint32_t n_ct, uint32_t level, const int64_t* h_k,

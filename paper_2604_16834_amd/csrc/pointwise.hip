@@ -284,6 +284,22 @@ hipError_t launch_ct_sum(const ckks_ctx* c, u32 level, const PtrList8& items, u3
     return hipGetLastError();
 }
 
+// ---- ct[0][i] += pt[i] on limbs 0..level (a plaintext, e.g. the replicated bias of the FC layer) -----------
+__global__ __launch_bounds__(PW_THREADS) void add_plain_kernel(const u64* __restrict__ pt, u64* __restrict__ ct,
+                                                               const ModConst* __restrict__ mc, u32 N) {
+    const u32 x = blockIdx.x * PW_THREADS + threadIdx.x;
+    if (x >= N) return;
+    const u32 i = blockIdx.y;
+    const size_t o = (size_t)i * N + x;
+    ct[o] = add_mod(ct[o], pt[o], mc[i].q);
+}
+
+hipError_t launch_add_plain(const ckks_ctx* c, u32 level, const u64* pt, u64* ct, hipStream_t st) {
+    dim3 grid((c->N + PW_THREADS - 1) / PW_THREADS, level + 1);
+    hipLaunchKernelGGL(add_plain_kernel, grid, dim3(PW_THREADS), 0, st, pt, ct, c->d_mc, c->N);
+    return hipGetLastError();
+}
+
 // ---- out_b = ka * a_b + kb * b_b (+ add_b) on limbs 0..level, integer scalars given by residues ----
 struct Scalars {
     u64 ka[CKKS_MAX_MODULI];

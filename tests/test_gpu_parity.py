@@ -298,6 +298,87 @@ def test_accumulator_merge_rejects_overfull_and_wrong_keys():
     assert e.value.code == hx.binding.CKKS_ERR_NO_KEY
 
 
+# ------------------------------------------------------------------------------ fully connected
+def fc_case(d_in, d_out, batch, base, log_n=10, seed=500):
+    p = make_params(log_n, 6, 2, 3)
+    orc, ctx = both(p)
+    level = p.num_q - 1
+    s, s_ntt = orc.gen_secret(seed)
+    rng = np.random.default_rng(seed + 1)
+    W = rng.normal(0, 0.3, (d_out, d_in))
+    bias = rng.uniform(-0.5, 0.5, d_out)
+    X = rng.uniform(-1, 1, (batch, d_in))
+    z = np.zeros(orc.n)
+    z[:batch * d_in] = X.reshape(-1)
+    scale = 2.0 ** 40
+    ct = orc.encrypt(z, scale, level, s_ntt, seed + 2)
+    delta, lo, hi = orc.fc_shifts(d_in, d_out, batch, base)
+    sums = [2 ** t for t in range(d_in.bit_length() - 1)]
+    merges = [-i for i in range(d_out)]
+    offsets = sorted({r for r in sums + merges + lo + hi if r % orc.n})
+    keys = {r: orc.gen_rotation_key(s, s_ntt, r, seed + 10 + k) for k, r in enumerate(offsets)}
+    dkeys = {r: hx.ckks_key_load(ctx, hx.from_host(k), hx.ckks_galois_element(ctx, r)) for r, k in keys.items()}
+    ops = orc.fc_operands(W, bias, batch, level, base, scale)
+    want = orc.fc_batched(ct, level, d_in, d_out, batch, base, *ops, keys)
+    w_enc, merge_mask, place, bias_pt = [hx.from_host(a) for a in ops]
+    pick = lambda offs: [dkeys.get(r) for r in offs]
+    run = lambda **kw: hx.he_fc_batched(ctx, hx.from_host(ct), level, d_in, d_out, batch, base, w_enc, merge_mask, place, bias_pt,
+                                        pick(sums), pick(merges), pick(lo), pick(hi), **kw)
+    return dict(orc=orc, ctx=ctx, level=level, s_ntt=s_ntt, scale=scale, X=X, W=W, bias=bias, want=want, run=run, dkeys=dkeys,
+                args=(sums, merges, lo, hi))
+
+
+@pytest.mark.parametrize("d_in,d_out,batch,base", [(16, 4, 8, 3), (8, 8, 4, 2), (32, 10, 16, 4), (64, 10, 8, 1), (16, 1, 5, 8)])
+def test_fc_batched_matches_oracle(d_in, d_out, batch, base):
+    """Residues against the oracle and slots against W x + b: ragged base blocks (8 = 3+3+2), d_out = d_in (no layout
+    rotation), ten outputs (two batches of merge rotations), base 1 (only second rotations), base > batch (only first
+    rotations), one output (no merge rotation)."""
+    k = fc_case(d_in, d_out, batch, base)
+    orc, level = k["orc"], k["level"]
+    got = hx.to_host(k["run"]())
+    assert got.shape == (2, level - 2, orc.N)
+    assert np.array_equal(got, k["want"])
+    dec = orc.decrypt(got, level - 3, k["s_ntt"], k["scale"])
+    want = (k["X"] @ k["W"].T + k["bias"]).reshape(-1)
+    assert np.abs(dec[:batch * d_out] - want).max() < 1e-4
+    assert np.abs(dec[batch * d_out:]).max() < 1e-4
+
+
+def test_fc_batched_spans_tiles_and_reuses_its_workspace():
+    """N = 2^12 (several tiles of every kernel), the classifier's 64 -> 10 shape, twice in the same workspace."""
+    d_in, d_out, batch, base = 64, 10, 32, 6
+    k = fc_case(d_in, d_out, batch, base, log_n=12, seed=540)
+    ctx, level = k["ctx"], k["level"]
+    ws = hx.empty(hx.he_fc_workspace_bytes(ctx, d_in, d_out, batch, level, base) // 8)
+    ws.fill_(-1)
+    a = hx.to_host(k["run"](ws=ws))
+    b = hx.to_host(k["run"](ws=ws))
+    assert np.array_equal(a, k["want"]) and np.array_equal(b, k["want"])
+
+
+def test_fc_batched_rejects_bad_shapes_and_keys():
+    k = fc_case(16, 4, 8, 3)
+    ctx, level, orc = k["ctx"], k["level"], k["orc"]
+    sums, merges, lo, hi = k["args"]
+    ct = hx.empty(2, level + 1, orc.N)
+    w = hx.empty(4, level + 1, orc.N)
+    mm, pm, b = hx.empty(level, orc.N), hx.empty(8, level - 1, orc.N), hx.empty(level - 2, orc.N)
+    pick = lambda offs: [k["dkeys"].get(r) for r in offs]
+    good = [pick(sums), pick(merges), pick(lo), pick(hi)]
+    for i in range(4):                                        # a missing or mismatched key in each list
+        lists = [list(x) for x in good]
+        lists[i][-1] = None if i else lists[i][0]
+        with pytest.raises(hx.CkksError) as e:
+            hx.he_fc_batched(ctx, ct, level, 16, 4, 8, 3, w, mm, pm, b, *lists)
+        assert e.value.code == hx.binding.CKKS_ERR_NO_KEY
+    with pytest.raises(hx.CkksError) as e:                    # d_in not a power of two
+        hx.he_fc_batched(ctx, ct, level, 12, 4, 8, 3, w, mm, pm, b, pick(sums)[:3], pick(merges), pick(lo), pick(hi))
+    assert e.value.code == hx.binding.CKKS_ERR_INVALID_ARG
+    with pytest.raises(hx.CkksError) as e:                    # too small a workspace
+        hx.he_fc_batched(ctx, ct, level, 16, 4, 8, 3, w, mm, pm, b, *good, ws=hx.empty(1024))
+    assert e.value.code == hx.binding.CKKS_ERR_WORKSPACE_TOO_SMALL
+
+
 # ------------------------------------------------------------------------------------ activation
 @pytest.mark.parametrize("n_ct", [1, 3, 10])
 def test_poly_activation_matches_oracle(n_ct):
