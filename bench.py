@@ -293,6 +293,37 @@ def main():
     torch.cuda.synchronize()
     result["accumulator_merges_per_s"] = reps / (time.perf_counter() - t0)
     result["accumulator_merge_shape"] = {"g": acc_g, "sts": acc_sts, "level": acc_level}
+    # batched fully connected layer at the classifier's shape: 64 -> 10 on 512 images (all N/2 slots), level 3,
+    # base = ceil(sqrt(512)); every one of its 59 rotations has a key tensor of its own (random residues)
+    fc_in, fc_out, fc_batch, fc_level, fc_base = 64, 10, 512, 3, 23
+    fc_delta = fc_in - fc_out
+    fc_offs = [[1 << t for t in range(6)], [-i for i in range(fc_out)], [l * fc_delta for l in range(fc_base)],
+               [h * fc_base * fc_delta for h in range(-(-fc_batch // fc_base))]]
+    fc_keys = [[None if r % (N // 2) == 0 else
+                hx.ckks_key_load(ctx, base_keys[(7 * i + j) % len(base_keys)].tensor.clone(), hx.ckks_galois_element(ctx, r))
+                for j, r in enumerate(offs)] for i, offs in enumerate(fc_offs)]
+    fc_ct = ins[0][:, :fc_level + 1].contiguous()
+    fc_w = torch.stack([masks[i % 9, :fc_level + 1] for i in range(fc_out)]).contiguous()
+    fc_mm = masks[0, :fc_level].contiguous()
+    fc_pm = torch.stack([masks[i % 9, :fc_level - 1] for i in range(fc_batch)]).contiguous()
+    fc_b = masks[1, :fc_level - 2].contiguous()
+    fc_o = hx.empty(2, fc_level - 2, N)
+    fc_ws = hx.empty(hx.he_fc_workspace_bytes(ctx, fc_in, fc_out, fc_batch, fc_level, fc_base) // 8)
+    run_fc = lambda: hx.he_fc_batched(ctx, fc_ct, fc_level, fc_in, fc_out, fc_batch, fc_base, fc_w, fc_mm, fc_pm, fc_b,
+                                      *fc_keys, out=fc_o, ws=fc_ws)
+    run_fc()
+    torch.cuda.synchronize()
+    reps = 10
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        run_fc()
+    torch.cuda.synchronize()
+    fc_dt = (time.perf_counter() - t0) / reps
+    result["fc_layer_ms"] = fc_dt * 1e3
+    result["fc_layer_ms_per_image"] = fc_dt * 1e3 / fc_batch
+    result["fc_layer_shape"] = {"d_in": fc_in, "d_out": fc_out, "batch": fc_batch, "level": fc_level, "base": fc_base,
+                                "key_switches": sum(k is not None for ks in fc_keys for k in ks) + (fc_out - 1) * 6}
+    del fc_keys, fc_ws
     # NTT microbenchmark: 64 polynomials x 30 limbs at N = 2^16, forward then inverse
     p2 = CONFIGS["cfg2_ntt"].params()
     ctx2 = hx.Context(p2)

@@ -903,14 +903,12 @@ int he_fc_batched(const ckks_ctx* c, const he_fc_desc* d, const uint64_t* d_in, 
     }
     u64* out = (u64*)d_out;
     {
-        bool first = true;
-        for (u32 h0 = 0; h0 < n_hi; h0 += KS_MAX_BATCH - 1) {
+        for (u32 h = 0; h < n_hi;) {  // the running sum is one of the terms of every launch after the first
             const u64* terms[KS_MAX_BATCH];
             u32 nt = 0;
-            if (!first) terms[nt++] = out;
-            for (u32 h = h0; h < n_hi && nt < KS_MAX_BATCH; h++) terms[nt++] = h == 0 ? V : Vrot + h * ct3;
+            if (h) terms[nt++] = out;
+            for (; h < n_hi && nt < KS_MAX_BATCH; h++) terms[nt++] = h == 0 ? V : Vrot + h * ct3;
             HIP_TRY(launch_ct_sum(c, l3, ptr_list(terms, nt), nt, out, st));
-            first = false;
         }
     }
     // 4. bias on component 0

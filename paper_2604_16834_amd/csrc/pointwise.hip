@@ -265,7 +265,8 @@ hipError_t launch_weighted_sum(const ckks_ctx* c, u32 level, bool extended, cons
 }
 
 // ---- out = sum of n <= KS_MAX_BATCH ciphertexts [2][level+1][N] (the accumulator's additions) ----------
-__global__ __launch_bounds__(PW_THREADS) void ct_sum_kernel(PtrList8 items, u32 n, u64* __restrict__ out,
+__global__ __launch_bounds__(PW_THREADS) void ct_sum_kernel(PtrList8 items, u32 n, u64* out,  // out may be one of the items
+                                                           
                                                             const ModConst* __restrict__ mc, u32 N, u32 level) {
     const u32 x = blockIdx.x * PW_THREADS + threadIdx.x;
     if (x >= N) return;

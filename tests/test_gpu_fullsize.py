@@ -185,3 +185,34 @@ def test_accumulator_merge_at_the_block_group_transition():
     assert np.array_equal(out, orc.accumulator_merge(cts, level, sts, M, keys))
     want = np.concatenate([z[:sts] for z in zs])
     assert np.abs(orc.decrypt(out, level - 1, s_ntt, scale) - want).max() < 1e-5
+
+
+def test_fc_batched_at_the_classifier_shape():
+    """The classifier of the batched ResNet-20: 64 -> 10 on 512 images in one ciphertext (every one of the N/2 slots
+    in use) at N = 2^16, at the lowest level the layer can run on (3), base = ceil(sqrt(512)) = 23 (23 first and 23
+    second layout rotations, the last base block ragged): residues against the oracle, slots against W x + b."""
+    wl = CONFIGS["cfg5_resnet20_stage3"]
+    p = wl.params()
+    orc, ctx = Oracle(p), hx.Context(p)
+    d_in, d_out, batch, base, level = 64, 10, 512, 23, 3
+    s, s_ntt = orc.gen_secret(7000)
+    rng = np.random.default_rng(7001)
+    W = rng.normal(0, (2.0 / d_in) ** 0.5, (d_out, d_in))
+    bias = rng.uniform(-0.5, 0.5, d_out)
+    X = rng.uniform(0, 1, (batch, d_in))              # pooled activations
+    scale = 2.0 ** 40
+    ct = orc.encrypt(X.reshape(-1), scale, level, s_ntt, 7002)
+    delta, lo, hi = orc.fc_shifts(d_in, d_out, batch, base)
+    sums = [2 ** t for t in range(6)]
+    merges = [-i for i in range(d_out)]
+    offsets = sorted({r for r in sums + merges + lo + hi if r % orc.n})
+    keys = {r: orc.gen_rotation_key(s, s_ntt, r, 7100 + k) for k, r in enumerate(offsets)}
+    dkeys = {r: hx.ckks_key_load(ctx, hx.from_host(k), hx.ckks_galois_element(ctx, r)) for r, k in keys.items()}
+    ops = orc.fc_operands(W, bias, batch, level, base, scale)
+    pick = lambda offs: [dkeys.get(r) for r in offs]
+    got = hx.to_host(hx.he_fc_batched(ctx, hx.from_host(ct), level, d_in, d_out, batch, 0, *[hx.from_host(a) for a in ops],
+                                      pick(sums), pick(merges), pick(lo), pick(hi)))      # base 0: the library's default
+    assert np.array_equal(got, orc.fc_batched(ct, level, d_in, d_out, batch, base, *ops, keys))
+    dec = orc.decrypt(got, level - 3, s_ntt, scale)
+    assert np.abs(dec[:batch * d_out] - (X @ W.T + bias).reshape(-1)).max() < 1e-4
+    assert np.abs(dec[batch * d_out:]).max() < 1e-4

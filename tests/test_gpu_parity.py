@@ -328,11 +328,13 @@ def fc_case(d_in, d_out, batch, base, log_n=10, seed=500):
                 args=(sums, merges, lo, hi))
 
 
-@pytest.mark.parametrize("d_in,d_out,batch,base", [(16, 4, 8, 3), (8, 8, 4, 2), (32, 10, 16, 4), (64, 10, 8, 1), (16, 1, 5, 8)])
+@pytest.mark.parametrize("d_in,d_out,batch,base", [(16, 4, 8, 3), (8, 8, 4, 2), (32, 10, 16, 4), (64, 10, 8, 1), (16, 1, 5, 8),
+                                                   (8, 2, 40, 2), (8, 2, 40, 20)])
 def test_fc_batched_matches_oracle(d_in, d_out, batch, base):
     """Residues against the oracle and slots against W x + b: ragged base blocks (8 = 3+3+2), d_out = d_in (no layout
     rotation), ten outputs (two batches of merge rotations), base 1 (only second rotations), base > batch (only first
-    rotations), one output (no merge rotation)."""
+    rotations), one output (no merge rotation), 20 second rotations (three batches, a final sum in two launches),
+    20 first rotations (three batches)."""
     k = fc_case(d_in, d_out, batch, base)
     orc, level = k["orc"], k["level"]
     got = hx.to_host(k["run"]())
