@@ -229,7 +229,13 @@ def main():
             lane_ops, unit = ALU_KERNELS[dom]
             peak = ALU_PEAK_LANE_OPS / lane_ops / 1e9
             ach = v["ops"] / secs / 1e9
-            roof.update({"bound": "alu", "achieved": ach, "peak": peak, "unit": unit, "frac": ach / peak})
+            hbm = v["bytes"] / secs / 1e9
+            if hbm / HBM_PEAK_GBS > ach / peak:   # the roofline that binds is the one the kernel sits closer to
+                roof.update({"bound": "hbm", "achieved": hbm, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": hbm / HBM_PEAK_GBS,
+                             "alu": {"achieved": ach, "peak": peak, "unit": unit, "frac": ach / peak}})
+            else:
+                roof.update({"bound": "alu", "achieved": ach, "peak": peak, "unit": unit, "frac": ach / peak,
+                             "hbm": {"achieved": hbm, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": hbm / HBM_PEAK_GBS}})
         else:
             ach = v["bytes"] / secs / 1e9
             roof.update({"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS})
