@@ -599,6 +599,76 @@ class Oracle:
             total = t if total is None else self.add(total, t, level)
         return self.rescale(total, level)
 
+    # ------------------------------------------------- slot re-layout with two rotations per element
+    def relayout_two_rotations(self, ct, level: int, lo: Sequence[int], hi: Sequence[int], masks, keys: Dict[int, np.ndarray]) -> np.ndarray:
+        """The two-rotation placement of the FC layer's output reconstruction ("Fully Connected Layer": every
+        element moves by base_idx + mod_idx), as an operation of its own:
+            out = sum_h Rot( Rescale( sum_l M[h][l] (.) Rot(ct, lo[l]) ), hi[h] ),
+        an element that has to move left by lo[l] + hi[h] is selected by the mask M[h][l] (given in NTT form
+        [level+1][N], or None when no element takes that pair) after its first rotation.  The first rotations
+        share one decomposition of ct.  Result [2][level][N] at level-1."""
+        ct = _u64(ct)
+        digits = self.modup(ct[1], level)
+        R = [self.rotate(ct, level, r, keys.get(r), True, digits) for r in lo]
+        out = None
+        for h in range(len(hi)):
+            ls = [l for l in range(len(lo)) if masks[h][l] is not None]
+            V = self.rescale(self.ptct_mac([masks[h][l] for l in ls], [R[l] for l in ls], level), level)
+            V = self.rotate(V, level - 1, hi[h], keys.get(hi[h]), True)
+            out = V if out is None else self.add(out, V, level - 1)
+        return out
+
+    def downsample_plan(self, height: int, width: int, batch: int, r: int = 2, base: int = 0):
+        """Slot compaction after a stride-r layer ("Optimized Inference Pipeline": H' = H/r, W' = W/r, sts' = sts/r^2;
+        the paper leaves the compaction itself to its library).  Input layout: image j at slots [j*H*W, (j+1)*H*W)
+        with the kept elements (y, x) = (r y', r x') at j*H*W + r*y'*W + r*x'.  Output layout: image j at slots
+        [j*H'*W', (j+1)*H'*W'), everything else zero.  Two re-layouts of two rotations each:
+          A (inside every image):  element (y', x') moves left by x'*(r-1) [lo] + y'*(r*W - W') [hi];
+          B (whole images):        image j moves left by j*(H*W - H'*W') = (j % base)*d [lo] + (j // base)*base*d [hi].
+        Returns [(lo, hi, slot_masks)] for A and B; slot_masks[h][l] is a 0/1 vector over the n slots (the positions of
+        the selected elements after their first rotation) or None."""
+        assert height % r == 0 and width % r == 0 and batch * height * width <= self.n
+        hw, h2, w2 = height * width, height // r, width // r
+        base = base or int(np.ceil(np.sqrt(batch)))
+        j0 = np.arange(batch) * hw
+        lo_a = [x * (r - 1) for x in range(w2)]
+        hi_a = [y * (r * width - w2) for y in range(h2)]
+        masks_a = []
+        for y in range(h2):
+            row = []
+            for x in range(w2):
+                m = np.zeros(self.n)
+                m[j0 + r * y * width + r * x - lo_a[x]] = 1.0
+                row.append(m)
+            masks_a.append(row)
+        d = hw - h2 * w2
+        lo_b = [l * d for l in range(min(base, batch))]
+        hi_b = [h * base * d for h in range(-(-batch // base))]
+        masks_b = []
+        for h in range(len(hi_b)):
+            row = []
+            for l in range(len(lo_b)):
+                j = h * base + l
+                if j >= batch:
+                    row.append(None)
+                    continue
+                m = np.zeros(self.n)
+                start = j * hw - lo_b[l]
+                m[start:start + h2 * w2] = 1.0
+                row.append(m)
+            masks_b.append(row)
+        return [(lo_a, hi_a, masks_a), (lo_b, hi_b, masks_b)]
+
+    def downsample_compact(self, ct, level: int, plan, keys: Dict[int, np.ndarray]) -> np.ndarray:
+        """Runs the two re-layouts of downsample_plan; every mask is encoded at the scale of the limb its product
+        drops, so the ciphertext's scale is unchanged.  Input at `level`, output [2][level-1][N] at level-2."""
+        ct = _u64(ct)
+        for stage, (lo, hi, slot_masks) in enumerate(plan):
+            lv = level - stage
+            masks = [[None if m is None else self.encode_ntt(m, float(self.moduli[lv]), lv) for m in row] for row in slot_masks]
+            ct = self.relayout_two_rotations(ct, lv, lo, hi, masks, keys)
+        return ct
+
     # ------------------------------------------- ciphertext product with the merged division
     def ctct_mul_relin_rescale(self, a, b, rlk, level: int, addend=None) -> np.ndarray:
         """Rescale(a*b + addend) with the relinearisation's division by P and the rescale's division by
@@ -707,15 +777,8 @@ class Oracle:
         U = self.accumulator_merge(S, level - 1, 1, merge_mask, {-i: keys[-i] for i in range(1, d_out)})
         # 3. layout
         l2 = level - 2
-        digits = self.modup(U[1], l2)
-        R = [U if l == 0 else self.rotate(U, l2, lo[l], keys.get(lo[l]), True, digits) for l in range(len(lo))]
-        out = None
-        for h in range(len(hi)):
-            js = [h * base + l for l in range(len(lo)) if h * base + l < batch]
-            V = self.rescale(self.ptct_mac([place_masks[j] for j in js], [R[j % base] for j in js], l2), l2)
-            if h:
-                V = self.rotate(V, l2 - 1, hi[h], keys.get(hi[h]), True)
-            out = V if out is None else self.add(out, V, l2 - 1)
+        masks = [[place_masks[h * base + l] if h * base + l < batch else None for l in range(len(lo))] for h in range(len(hi))]
+        out = self.relayout_two_rotations(U, l2, lo, hi, masks, keys)
         # 4. bias
         out = out.copy()
         for i in range(l2):

@@ -270,6 +270,100 @@ def test_accumulator_merge_concatenates_cleaned_blocks():
         o.accumulator_merge(cts * 2, level, sts, M, keys)
 
 
+def downsample_keys(o, s, s_ntt, plan, seed):
+    offs = sorted({r for lo, hi, _ in plan for r in list(lo) + list(hi) if r % o.n})
+    return {r: o.gen_rotation_key(s, s_ntt, r, seed + k) for k, r in enumerate(offs)}
+
+
+@pytest.mark.parametrize("height,width,batch,r,base", [(4, 4, 8, 2, 3), (4, 8, 5, 2, 0), (8, 8, 2, 4, 1), (2, 2, 16, 2, 16)])
+def test_downsample_compaction_is_the_strided_selection(height, width, batch, r, base):
+    """Every image keeps its elements (r y', r x') and the kept elements of image j end up row-major in slots
+    [j H'W', (j+1) H'W'); the dropped elements and the unused slots decrypt to zero (float64 reference: numpy slicing)."""
+    p = make_params(10, 5, 2, 3)
+    o = Oracle(p)
+    level = p.num_q - 1
+    s, s_ntt = o.gen_secret(14000)
+    X = np.random.default_rng(11).uniform(-1, 1, (batch, height, width))
+    z = np.random.default_rng(12).uniform(-1, 1, o.n)          # junk behind the images: it has to vanish
+    z[:X.size] = X.reshape(-1)
+    scale = 2.0 ** 40
+    ct = o.encrypt(z, scale, level, s_ntt, 14001)
+    plan = o.downsample_plan(height, width, batch, r, base)
+    out = o.downsample_compact(ct, level, plan, downsample_keys(o, s, s_ntt, plan, 14100))
+    assert out.shape == (2, level - 1, o.N)
+    got = o.decrypt(out, level - 2, s_ntt, scale)
+    want = X[:, ::r, ::r].reshape(-1)
+    assert np.abs(got[:want.size] - want).max() < 1e-5
+    assert np.abs(got[want.size:]).max() < 1e-5
+
+
+def test_downsample_plan_moves_every_kept_slot_exactly_once():
+    """The plan alone, on slot indices: following mask -> first rotation -> second rotation sends the slot of every kept
+    element to its compact position, no two masks of a stage overlap after their rotations, and the slot accounting of the
+    pipeline holds (sts' = sts / r^2)."""
+    o = Oracle(make_params(10, 1, 0, 1))
+    height, width, batch, r = 4, 8, 7, 2
+    (lo_a, hi_a, m_a), (lo_b, hi_b, m_b) = o.downsample_plan(height, width, batch, r, 3)
+    pos = {}                                                       # slot -> (j, y', x') through the stages
+    for j in range(batch):
+        for y in range(height // r):
+            for x in range(width // r):
+                pos[j * height * width + r * y * width + r * x] = (j, y, x)
+    for lo, hi, masks in ((lo_a, hi_a, m_a), (lo_b, hi_b, m_b)):
+        nxt = {}
+        for h, row in enumerate(masks):
+            for l, m in enumerate(row):
+                if m is None:
+                    continue
+                for slot in np.flatnonzero(m):
+                    src = int(slot) + lo[l]                        # where the selected slot was before the first rotation
+                    assert src in pos, "a mask selects a slot that holds no kept element"
+                    dst = int(slot) - hi[h]
+                    assert dst not in nxt
+                    nxt[dst] = pos.pop(src)
+        assert not pos, "a kept element is selected by no mask"
+        pos = nxt
+    h2, w2 = height // r, width // r
+    assert pos == {j * h2 * w2 + y * w2 + x: (j, y, x) for j in range(batch) for y in range(h2) for x in range(w2)}
+    assert len(pos) * r * r == batch * height * width
+
+
+def test_strided_conv_then_accumulator_fills_the_ciphertext():
+    """The block-group transition end to end: g = 4 tiles of images go through a 3x3 convolution, are down-sampled with
+    stride 2 and merged by the accumulator into one ciphertext holding 4x the images at the smaller size; the slots
+    equal the stride-2 convolution (float64 reference, sliced) of all tiles side by side."""
+    p = make_params(10, 6, 2, 3)
+    o = Oracle(p)
+    level = p.num_q - 1
+    height = width = 4
+    batch, g, c_in = 8, 4, 2
+    s, s_ntt = o.gen_secret(15000)
+    scale = 2.0 ** 40
+    w = conv_weights(1, c_in, dist="he_normal")
+    offs = conv_tap_offsets(width)
+    keys = {off: o.gen_rotation_key(s, s_ntt, off, 15100 + i) for i, off in enumerate(offs) if off}
+    M, w_int = o.conv_operands(w, height, width, batch, level, 2.0 ** 28, p.moduli[level] / 2.0 ** 28)
+    plan = o.downsample_plan(height, width, batch, 2, 3)
+    dkeys = downsample_keys(o, s, s_ntt, plan, 15200)
+    sts2 = batch * height * width // 4
+    tiles, refs = [], []
+    for t in range(g):
+        img = image_batch(batch, c_in, height, width, seed=15300 + t)
+        cts = [o.encrypt(o.pack_channel(img, c), scale, level, s_ntt, 15400 + 10 * t + c) for c in range(c_in)]
+        conv = o.he_conv(cts, level, width, keys, M, w_int)[0]                       # level-1
+        tiles.append(o.downsample_compact(conv, level - 1, plan, dkeys))            # level-3
+        refs.append(conv2d_reference(img, w)[:, 0, ::2, ::2].reshape(-1))
+    lm = level - 3
+    Mc = o.encode_ntt(o.cleaning_mask(sts2), float(p.moduli[lm]), lm)
+    mkeys = {-i * sts2: o.gen_rotation_key(s, s_ntt, -i * sts2, 15500 + i) for i in range(1, g)}
+    joined = o.accumulator_merge(tiles, lm, sts2, Mc, mkeys)
+    got = o.decrypt(joined, lm - 1, s_ntt, scale)
+    want = np.concatenate(refs)
+    assert want.size == g * sts2 == batch * height * width                            # the ciphertext's images are full again
+    assert np.abs(got[:want.size] - want).max() < 1e-4
+    assert np.abs(got[want.size:]).max() < 1e-4
+
+
 def test_activation_polynomial_pins():
     assert activation_reference(np.array([0.0, 1.0, -1.0])).tolist() == [0.0, 1.0, -1.0]
     # p'(x) = 35/16 (1-x^2)^3: flat at +-1
