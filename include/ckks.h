@@ -195,6 +195,24 @@ int he_accumulator_merge(const ckks_ctx* ctx, const uint64_t* const* h_d_cts, ui
                          const uint64_t* d_mask, const ckks_key* const* keys, uint64_t* d_out, void* d_ws,
                          size_t ws_bytes, void* stream);
 
+/* Slot re-layout with two rotations per element: the output reconstruction of the FC layer ("Fully Connected
+ * Layer": every element moves by base_idx + mod_idx with two rotation keys) as an operation of its own, applied to
+ * the n_ct ciphertexts of a channel vector (they share keys and masks):
+ *   out_b = sum_h Rot( Rescale( sum_l M[h][l] (.) Rot(ct_b, lo[l]) ), hi[h] )
+ * An element that has to move left by lo[l] + hi[h] slots is selected by the mask M[h][l] after its first rotation.
+ * It is what compacts the slots after a stride-r layer ("Optimized Inference Pipeline": H' = H/r, W' = W/r,
+ * sts' = sts/r^2) in front of he_accumulator_merge: once inside every image (lo = x'(r-1), hi = y'(rW - W')), once
+ * over whole images (lo = (j mod base) d, hi = (j div base) base d, d = HW - H'W').
+ * h_d_cts[b] uint64[2][level+1][N], level >= 1; h_lo / h_hi: host arrays of slot offsets (0 = no rotation, key
+ * ignored); lo_keys[l] / hi_keys[h] made for those offsets; h_d_masks: host array of n_hi*n_lo device pointers,
+ * entry h*n_lo + l is uint64[level+1][N] (NTT form) or NULL when no element takes that pair (every h needs one
+ * mask at least); h_d_outs[b] uint64[2][level][N], one level lower.  Outputs must not overlap inputs. */
+size_t he_relayout_workspace_bytes(const ckks_ctx* ctx, uint32_t level, uint32_t n_ct, uint32_t n_lo, uint32_t n_hi);
+int he_relayout_two_rotations(const ckks_ctx* ctx, const uint64_t* const* h_d_cts, uint32_t n_ct, uint32_t level,
+                              const int32_t* h_lo, uint32_t n_lo, const ckks_key* const* lo_keys, const int32_t* h_hi,
+                              uint32_t n_hi, const ckks_key* const* hi_keys, const uint64_t* const* h_d_masks,
+                              uint64_t* const* h_d_outs, void* d_ws, size_t ws_bytes, void* stream);
+
 /* Batched fully connected layer ("Fully Connected Layer": FC evaluation and output reconstruction).  The input
  * ciphertext holds x^(j) (d_in values, d_in a power of two) in slots [j*d_in, (j+1)*d_in) for j < batch
  * (batch*d_in <= N/2); the output, three levels lower, holds W x^(j) + bias in slots [j*d_out, (j+1)*d_out).

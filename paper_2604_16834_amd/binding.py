@@ -43,6 +43,7 @@ EXPORTS = (
     "ckks_keyswitch", "ckks_rotate_hoisted", "ckks_ptct_mac", "ckks_rescale", "ckks_ctct_mul_relin",
     "he_conv_workspace_bytes", "he_conv_batched", "he_poly_act_deg7",
     "he_accumulator_workspace_bytes", "he_accumulator_merge", "he_fc_workspace_bytes", "he_fc_batched",
+    "he_relayout_workspace_bytes", "he_relayout_two_rotations",
     "ckks_prof_kernel_count", "ckks_prof_kernel_name", "ckks_prof_begin", "ckks_prof_end",
 )
 
@@ -104,6 +105,10 @@ def _bind(path: str):
     lib.he_fc_workspace_bytes.restype = sz
     lib.he_fc_batched.argtypes = [vp, C.POINTER(_FcDesc), vp, vp, C.POINTER(vp), C.POINTER(vp), vp, vp, C.POINTER(vp), C.POINTER(vp),
                                   vp, vp, vp, sz, vp]
+    lib.he_relayout_workspace_bytes.argtypes = [vp, u32, u32, u32, u32]
+    lib.he_relayout_workspace_bytes.restype = sz
+    lib.he_relayout_two_rotations.argtypes = [vp, C.POINTER(vp), u32, u32, C.POINTER(C.c_int32), u32, C.POINTER(vp), C.POINTER(C.c_int32),
+                                              u32, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), vp, sz, vp]
     lib.ckks_prof_kernel_count.restype = u32
     lib.ckks_prof_kernel_name.argtypes = [u32]
     lib.ckks_prof_kernel_name.restype = C.c_char_p
@@ -403,6 +408,41 @@ def he_accumulator_merge(ctx: Context, cts: Sequence[torch.Tensor], level: int, 
     ctx._check(_lib.he_accumulator_merge(ctx.handle, ca, g, level, sts, _ptr(mask), ka, _ptr(out), _ptr(ws),
                                          ws.numel() * ws.element_size(), _stream(stream)))
     return out
+
+
+def he_relayout_workspace_bytes(ctx: Context, level: int, n_ct: int, n_lo: int, n_hi: int) -> int:
+    return int(_lib.he_relayout_workspace_bytes(ctx.handle, level, n_ct, n_lo, n_hi))
+
+
+def he_relayout_two_rotations(ctx: Context, cts: Sequence[torch.Tensor], level: int, lo: Sequence[int], lo_keys: Sequence[Optional[Key]],
+                              hi: Sequence[int], hi_keys: Sequence[Optional[Key]], masks: Sequence[Sequence[Optional[torch.Tensor]]],
+                              outs: Optional[Sequence[torch.Tensor]] = None, ws: Optional[torch.Tensor] = None,
+                              stream=None) -> List[torch.Tensor]:
+    """out_b = sum_h Rot(Rescale(sum_l masks[h][l] (.) Rot(cts[b], lo[l])), hi[h]); masks[h][l] is [level+1][N] or None.
+    cts[b] [2][level+1][N]; returns [2][level][N] per ciphertext."""
+    n_ct, n_lo, n_hi = len(cts), len(lo), len(hi)
+    if len(lo_keys) != n_lo or len(hi_keys) != n_hi or len(masks) != n_hi or any(len(row) != n_lo for row in masks):
+        raise ValueError("key and mask lists do not match the offsets")
+    for t in cts:
+        if t.numel() != 2 * (level + 1) * ctx.N:
+            raise ValueError("each ciphertext must be [2][level+1][N]")
+    for row in masks:
+        for m in row:
+            if m is not None and m.numel() != (level + 1) * ctx.N:
+                raise ValueError("each mask must be [level+1][N]")
+    if outs is None:
+        outs = [empty(2, max(level, 1), ctx.N) for _ in range(n_ct)]
+    for t in outs:
+        if t.numel() != 2 * level * ctx.N:
+            raise ValueError("each output must be [2][level][N]")
+    ws = _ws(ctx, ws, he_relayout_workspace_bytes(ctx, level, n_ct, n_lo, n_hi))
+    arr = lambda ks: _ptr_array([k.handle.value if k is not None else None for k in ks])
+    i32 = lambda v: (C.c_int32 * len(v))(*[int(x) for x in v])
+    ctx._check(_lib.he_relayout_two_rotations(ctx.handle, _ptr_array([_ptr(t) for t in cts]), n_ct, level, i32(lo), n_lo, arr(lo_keys),
+                                              i32(hi), n_hi, arr(hi_keys), _ptr_array([_ptr(m) for row in masks for m in row]),
+                                              _ptr_array([_ptr(t) for t in outs]), _ptr(ws), ws.numel() * ws.element_size(),
+                                              _stream(stream)))
+    return list(outs)
 
 
 def he_fc_workspace_bytes(ctx: Context, d_in: int, d_out: int, batch: int, level: int, base: int = 0) -> int:

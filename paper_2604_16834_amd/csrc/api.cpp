@@ -295,23 +295,28 @@ int conv_deferred(const ckks_ctx* c, const he_conv_desc* d, const u32* gs, const
     return CKKS_OK;
 }
 
-// n <= CT_BATCH different ciphertexts srcs[b] ([2][level+1][N]) rotated, outs[b] = Rot(srcs[b]) ([2][level+1][N], no overlap).
-// key_of(b) / gal[b]: one key for all (shared: the key streams once for the batch) or one per item.
-int run_rotate_batch(const ckks_ctx* c, u32 level, u32 n, const u64* const* srcs, const ckks_key* const* keys, bool shared_key,
-                     const u32* gal, u64* const* outs, const KsWs& ws, hipStream_t st) {
+// n <= CT_BATCH different ciphertexts srcs[b] ([2][level+1][N]) rotated, outs[b] = Rot(srcs[b]) with keys[b] / gal[b]
+// ([2][level+1][N], no overlap).  Neighbouring items with the same key go through one inner-product launch (the key
+// streams once for all of them).
+int run_rotate_batch(const ckks_ctx* c, u32 level, u32 n, const u64* const* srcs, const ckks_key* const* keys, const u32* gal,
+                     u64* const* outs, const KsWs& ws, hipStream_t st) {
     const size_t N = c->N, L1 = level + 1;
     const u64* c1s[CT_BATCH];
     FinalItem items[CT_BATCH];
     for (u32 b = 0; b < n; b++) c1s[b] = srcs[b] + L1 * N;
     int rc = run_modup(c, level, c1s, n, ws, st);
     if (rc) return rc;
-    if (shared_key) {
-        HIP_TRY(launch_key_inner_multi(c, level, ws.digits, ws.dig_b, keys[0]->d_key, gal[0], ws.v, ws.v_b, n, st));
-    } else {
-        for (u32 b = 0; b < n; b++)
-            HIP_TRY(launch_key_inner(c, level, ws.digits + b * ws.dig_b, keys[b]->d_key, gal[b], ws.v + b * ws.v_b, st));
+    for (u32 b0 = 0; b0 < n;) {
+        u32 b1 = b0 + 1;
+        while (b1 < n && keys[b1] == keys[b0]) b1++;
+        if (b1 - b0 == 1)
+            HIP_TRY(launch_key_inner(c, level, ws.digits + b0 * ws.dig_b, keys[b0]->d_key, gal[b0], ws.v + b0 * ws.v_b, st));
+        else
+            HIP_TRY(launch_key_inner_multi(c, level, ws.digits + b0 * ws.dig_b, ws.dig_b, keys[b0]->d_key, gal[b0], ws.v + b0 * ws.v_b,
+                                           ws.v_b, b1 - b0, st));
+        b0 = b1;
     }
-    for (u32 b = 0; b < n; b++) items[b] = FinalItem{srcs[b], nullptr, nullptr, outs[b], gal[shared_key ? 0 : b], 0};
+    for (u32 b = 0; b < n; b++) items[b] = FinalItem{srcs[b], nullptr, nullptr, outs[b], gal[b], 0};
     return run_moddown(c, level, ws, n, items, st);
 }
 
@@ -343,7 +348,7 @@ int run_merge(const ckks_ctx* c, const u64* const* cts, u32 g, u32 level, const 
             srcs[b] = masked + (i0 + b) * ct_elems;
             outs[b] = rotated + (i0 + b) * ct_elems;
         }
-        int rc = run_rotate_batch(c, level, n, srcs, keys + i0, false, gal + i0, outs, ws, st);
+        int rc = run_rotate_batch(c, level, n, srcs, keys + i0, gal + i0, outs, ws, st);
         if (rc) return rc;
     }
     const u64* terms[KS_MAX_BATCH];
@@ -352,6 +357,121 @@ int run_merge(const ckks_ctx* c, const u64* const* cts, u32 g, u32 level, const 
     HIP_TRY(launch_ct_sum(c, level, ptr_list(terms, g), g, total, st));
     const u64* in = total;
     return run_rescale(c, level, &in, L1 * N, &out, 1, ar.rest(), st);
+}
+
+// Slot re-layout with two rotations per element, for the n_ct ciphertexts of a channel vector (level `level`):
+//   outs[b] = sum_h Rot( Rescale( sum_l masks[h*n_lo+l] (.) Rot(cts[b], lo_l) ), hi_h )        ([2][level][N])
+// g_lo / g_hi: Galois elements (1 = no rotation, key ignored); masks: device pointers [level+1][N] or null; every h has
+// at least one mask (validated by the caller).  First rotations: one decomposition per ciphertext, every key read once per
+// batch of up to CT_BATCH (ciphertext, offset) pairs; second rotations batched the same way over (h, ciphertext).
+size_t ws_relayout(const ckks_ctx* c, u32 level, u32 n_ct, u32 n_lo, u32 n_hi) {
+    const size_t N = c->N, ctl = 2 * (size_t)(level + 1) * N, ctl1 = 2 * (size_t)level * N;
+    const size_t nb = n_ct < CT_BATCH ? n_ct : CT_BATCH;
+    return blk(nb * n_lo * ctl) + blk(nb * n_hi * ctl) + 2 * blk(nb * n_hi * ctl1) + ws_ks(c, level, CT_BATCH, CT_BATCH) +
+           ws_rescale(c, level, CT_BATCH);
+}
+
+int run_relayout(const ckks_ctx* c, u32 level, u32 n_ct, const u64* const* cts, u32 n_lo, const ckks_key* const* lo_keys, const u32* g_lo,
+                 u32 n_hi, const ckks_key* const* hi_keys, const u32* g_hi, const u64* const* masks, u64* const* outs, Arena ar,
+                 hipStream_t st) {
+    const size_t N = c->N, ctl = 2 * (size_t)(level + 1) * N, ctl1 = 2 * (size_t)level * N;
+    const u32 nb_max = n_ct < CT_BATCH ? n_ct : CT_BATCH, l1 = level - 1;
+    u64* R = ar.take((size_t)nb_max * n_lo * ctl);      // Rot(ct_b, lo_l)
+    u64* Vacc = ar.take((size_t)nb_max * n_hi * ctl);   // masked sums before their rescale
+    u64* V = ar.take((size_t)nb_max * n_hi * ctl1);     // level-1
+    u64* Vrot = ar.take((size_t)nb_max * n_hi * ctl1);
+    const size_t ks_bytes = ws_ks(c, level, CT_BATCH, CT_BATCH);
+    u64* ks_region = ar.take(ks_bytes / sizeof(u64));
+    if (!ar.ok() || ar.used + ws_rescale(c, level, CT_BATCH) > ar.cap)
+        return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for the re-layout");
+    KsWs ws;
+    auto ks_at = [&](u32 lv) {  // the key-switch buffers are carved again for the lower level
+        Arena sub(ks_region, ks_bytes);
+        return carve_ks(c, lv, CT_BATCH, CT_BATCH, sub, ws);
+    };
+    int rc;
+    for (u32 c0 = 0; c0 < n_ct; c0 += CT_BATCH) {
+        const u32 n = n_ct - c0 < CT_BATCH ? n_ct - c0 : CT_BATCH;
+        auto r_at = [&](u32 b, u32 l) { return R + ((size_t)b * n_lo + l) * ctl; };
+        // first rotations
+        ks_at(level);
+        const u64* c1s[CT_BATCH];
+        for (u32 b = 0; b < n; b++) c1s[b] = cts[c0 + b] + (size_t)(level + 1) * N;
+        if ((rc = run_modup(c, level, c1s, n, ws, st))) return rc;
+        const u32 per = CT_BATCH / n;  // offsets per ModDown batch
+        for (u32 la = 0; la < n_lo; la += per) {
+            FinalItem items[CT_BATCH];
+            u32 nk = 0;
+            for (u32 l = la; l < n_lo && l < la + per; l++) {
+                if (g_lo[l] == 1) {
+                    for (u32 b = 0; b < n; b++) HIP_TRY(launch_copy(cts[c0 + b], r_at(b, l), ctl, st));
+                    continue;
+                }
+                if (n == 1)
+                    HIP_TRY(launch_key_inner(c, level, ws.digits, lo_keys[l]->d_key, g_lo[l], ws.v + nk * ws.v_b, st));
+                else
+                    HIP_TRY(launch_key_inner_multi(c, level, ws.digits, ws.dig_b, lo_keys[l]->d_key, g_lo[l], ws.v + nk * ws.v_b, ws.v_b, n, st));
+                for (u32 b = 0; b < n; b++) items[nk++] = FinalItem{cts[c0 + b], nullptr, nullptr, r_at(b, l), g_lo[l], 0};
+            }
+            if (nk && (rc = run_moddown(c, level, ws, nk, items, st))) return rc;
+        }
+        // masked sums, one per (ciphertext, h), and their rescale
+        std::vector<const u64*> pts, rts;
+        for (u32 b = 0; b < n; b++)
+            for (u32 h = 0; h < n_hi; h++) {
+                pts.clear();
+                rts.clear();
+                for (u32 l = 0; l < n_lo; l++)
+                    if (masks[(size_t)h * n_lo + l]) {
+                        pts.push_back(masks[(size_t)h * n_lo + l]);
+                        rts.push_back(r_at(b, l));
+                    }
+                HIP_TRY(launch_ptct_mac(c, level, pts.data(), rts.data(), (u32)pts.size(), Vacc + ((size_t)b * n_hi + h) * ctl, 0, st));
+            }
+        const u32 n_v = n * n_hi;
+        for (u32 i0 = 0; i0 < n_v; i0 += CT_BATCH) {
+            const u32 m = n_v - i0 < CT_BATCH ? n_v - i0 : CT_BATCH;
+            const u64* pv[CT_BATCH];
+            u64* ov[CT_BATCH];
+            for (u32 i = 0; i < m; i++) {
+                pv[i] = Vacc + (size_t)(i0 + i) * ctl;
+                ov[i] = V + (size_t)(i0 + i) * ctl1;
+            }
+            if ((rc = run_rescale(c, level, pv, (size_t)(level + 1) * N, ov, m, ar.rest(), st))) return rc;
+        }
+        // second rotations, ordered by h so that the ciphertexts of a batch share each key
+        ks_at(l1);
+        const u64* srcs[CT_BATCH];
+        const ckks_key* ks[CT_BATCH];
+        u32 gs[CT_BATCH], nk = 0;
+        u64* dsts[CT_BATCH];
+        for (u32 h = 0; h < n_hi; h++) {
+            if (g_hi[h] == 1) continue;
+            for (u32 b = 0; b < n; b++) {
+                srcs[nk] = V + ((size_t)b * n_hi + h) * ctl1;
+                dsts[nk] = Vrot + ((size_t)b * n_hi + h) * ctl1;
+                ks[nk] = hi_keys[h];
+                gs[nk++] = g_hi[h];
+                if (nk == CT_BATCH) {
+                    if ((rc = run_rotate_batch(c, l1, nk, srcs, ks, gs, dsts, ws, st))) return rc;
+                    nk = 0;
+                }
+            }
+        }
+        if (nk && (rc = run_rotate_batch(c, l1, nk, srcs, ks, gs, dsts, ws, st))) return rc;
+        // the sums; the running sum is one of the terms of every launch after the first
+        for (u32 b = 0; b < n; b++) {
+            u64* out = outs[c0 + b];
+            for (u32 h = 0; h < n_hi;) {
+                const u64* terms[KS_MAX_BATCH];
+                u32 nt = 0;
+                if (h) terms[nt++] = out;
+                for (; h < n_hi && nt < KS_MAX_BATCH; h++) terms[nt++] = (g_hi[h] == 1 ? V : Vrot) + ((size_t)b * n_hi + h) * ctl1;
+                HIP_TRY(launch_ct_sum(c, l1, ptr_list(terms, nt), nt, out, st));
+            }
+        }
+    }
+    return CKKS_OK;
 }
 
 u32 ilog2(u32 v) { u32 r = 0; while ((1u << (r + 1)) <= v) r++; return r; }
@@ -733,6 +853,42 @@ int he_accumulator_merge(const ckks_ctx* c, const uint64_t* const* h_d_cts, uint
                      (hipStream_t)stream);
 }
 
+// ---- slot re-layout with two rotations per element (down-sampling compaction, FC output reconstruction) ----
+size_t he_relayout_workspace_bytes(const ckks_ctx* c, uint32_t level, uint32_t n_ct, uint32_t n_lo, uint32_t n_hi) {
+    if (!c || !c->dnum || !level_ok(c, level) || level < 1 || n_ct == 0 || n_lo == 0 || n_hi == 0) return 0;
+    return ws_relayout(c, level, n_ct, n_lo, n_hi);
+}
+
+int he_relayout_two_rotations(const ckks_ctx* c, const uint64_t* const* h_d_cts, uint32_t n_ct, uint32_t level, const int32_t* h_lo,
+                              uint32_t n_lo, const ckks_key* const* lo_keys, const int32_t* h_hi, uint32_t n_hi,
+                              const ckks_key* const* hi_keys, const uint64_t* const* h_d_masks, uint64_t* const* h_d_outs, void* d_ws,
+                              size_t ws_bytes, void* stream) {
+    if (!c) return CKKS_ERR_INVALID_ARG;
+    if (!h_d_cts || !h_lo || !h_hi || !h_d_masks || !h_d_outs || n_ct == 0 || n_lo == 0 || n_hi == 0)
+        return set_err(c, CKKS_ERR_INVALID_ARG, "null pointer or an empty list");
+    if (!c->dnum) return set_err(c, CKKS_ERR_UNSUPPORTED_PARAMS, "context has no key-switching digits");
+    if (!level_ok(c, level) || level < 1) return set_err(c, CKKS_ERR_LEVEL_MISMATCH, "the re-layout needs 1 <= level < num_q");
+    if ((u64)n_lo * n_hi > (u64)c->N) return set_err(c, CKKS_ERR_INVALID_ARG, "more (lo, hi) pairs than coefficients");
+    for (u32 b = 0; b < n_ct; b++)
+        if (!h_d_cts[b] || !h_d_outs[b]) return set_err(c, CKKS_ERR_INVALID_ARG, "null ciphertext pointer");
+    std::vector<u32> g_lo(n_lo), g_hi(n_hi);
+    for (u32 l = 0; l < n_lo; l++) {
+        g_lo[l] = ckks_galois_element(c, h_lo[l]);
+        if (g_lo[l] != 1 && (!lo_keys || !lo_keys[l] || lo_keys[l]->galois_elt != g_lo[l]))
+            return set_err(c, CKKS_ERR_NO_KEY, "key of a first rotation missing or made for another offset");
+    }
+    for (u32 h = 0; h < n_hi; h++) {
+        g_hi[h] = ckks_galois_element(c, h_hi[h]);
+        if (g_hi[h] != 1 && (!hi_keys || !hi_keys[h] || hi_keys[h]->galois_elt != g_hi[h]))
+            return set_err(c, CKKS_ERR_NO_KEY, "key of a second rotation missing or made for another offset");
+        bool any = false;
+        for (u32 l = 0; l < n_lo; l++) any = any || h_d_masks[(size_t)h * n_lo + l];
+        if (!any) return set_err(c, CKKS_ERR_INVALID_ARG, "a second rotation has no mask at all");
+    }
+    return run_relayout(c, level, n_ct, (const u64* const*)h_d_cts, n_lo, lo_keys, g_lo.data(), n_hi, hi_keys, g_hi.data(),
+                        (const u64* const*)h_d_masks, (u64* const*)h_d_outs, Arena(d_ws, ws_bytes), (hipStream_t)stream);
+}
+
 // ---- batched fully connected layer ------------------------------------------------------------------
 static u32 fc_base(const he_fc_desc* d) {
     if (d->base) return d->base;
@@ -741,13 +897,15 @@ static u32 fc_base(const he_fc_desc* d) {
     return b;
 }
 
+static size_t max3(size_t a, size_t b, size_t c3) { return a > b ? (a > c3 ? a : c3) : (b > c3 ? b : c3); }
+
 size_t he_fc_workspace_bytes(const ckks_ctx* c, const he_fc_desc* d) {
     if (!c || !d || !c->dnum || !level_ok(c, d->level) || d->level < 3 || d->d_out == 0 || d->d_out > KS_MAX_BATCH || d->batch == 0) return 0;
     const size_t N = c->N;
     const u32 level = d->level, base = fc_base(d), n_lo = base < d->batch ? base : d->batch, n_hi = (d->batch + base - 1) / base;
-    const size_t ct0 = 2 * (size_t)(level + 1) * N, ct1 = 2 * (size_t)level * N, ct2 = 2 * (size_t)(level - 1) * N, ct3 = 2 * (size_t)(level - 2) * N;
-    return blk(CT_BATCH * ct0) + blk(d->d_out * ct1) + blk(CT_BATCH * ct1) + blk(ct2) + blk(n_lo * ct2) + blk(n_hi * ct2) +
-           2 * blk(n_hi * ct3) + ws_ks(c, level - 1, CT_BATCH, CT_BATCH) + ws_merge(c, level - 1, d->d_out) + ws_rescale(c, level, CT_BATCH);
+    const size_t ct0 = 2 * (size_t)(level + 1) * N, ct1 = 2 * (size_t)level * N, ct2 = 2 * (size_t)(level - 1) * N;
+    return blk(CT_BATCH * ct0) + blk(d->d_out * ct1) + blk(CT_BATCH * ct1) + blk(ct2) + ws_ks(c, level - 1, CT_BATCH, CT_BATCH) +
+           max3(ws_merge(c, level - 1, d->d_out), ws_rescale(c, level, CT_BATCH), ws_relayout(c, level - 2, 1, n_lo, n_hi));
 }
 
 int he_fc_batched(const ckks_ctx* c, const he_fc_desc* d, const uint64_t* d_in, const uint64_t* d_w_enc, const ckks_key* const* sum_keys,
@@ -794,21 +952,11 @@ int he_fc_batched(const ckks_ctx* c, const he_fc_desc* d, const uint64_t* d_in, 
     u64* S = ar.take(d->d_out * ct1);           // running inner sums, level-1
     u64* Srot = ar.take(CT_BATCH * ct1);        // their rotations
     u64* U = ar.take(ct2);                      // merged, level-2
-    u64* R = ar.take(n_lo * ct2);               // Rot(U, l*delta)
-    u64* Vacc = ar.take(n_hi * ct2);            // masked sums before their rescale
-    u64* V = ar.take(n_hi * ct3);               // level-3
-    u64* Vrot = ar.take(n_hi * ct3);
-    // one key-switch region, sized for the highest level used and carved again for each lower level
-    const size_t ks_bytes = ws_ks(c, l1, CT_BATCH, CT_BATCH);
-    u64* ks_region = ar.take(ks_bytes / sizeof(u64));
-    if (!ar.ok() || ar.used + ws_merge(c, l1, d->d_out) > ar.cap || ar.used + ws_rescale(c, level, CT_BATCH) > ar.cap)
-        return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for the layer");
     KsWs ws;
-    auto ks_at = [&](u32 lv) {
-        Arena sub(ks_region, ks_bytes);
-        return carve_ks(c, lv, CT_BATCH, CT_BATCH, sub, ws);
-    };
-    if (!ks_at(l1)) return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for the layer");
+    bool ok = carve_ks(c, l1, CT_BATCH, CT_BATCH, ar, ws);
+    if (!ok || !ar.ok() ||
+        ar.used + max3(ws_merge(c, l1, d->d_out), ws_rescale(c, level, CT_BATCH), ws_relayout(c, l2, 1, n_lo, n_hi)) > ar.cap)
+        return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for the layer");
     hipStream_t st = (hipStream_t)stream;
     const u64* in = (const u64*)d_in;
     int rc;
@@ -825,8 +973,13 @@ int he_fc_batched(const ckks_ctx* c, const he_fc_desc* d, const uint64_t* d_in, 
         }
         if ((rc = run_rescale(c, level, pp, (size_t)(level + 1) * N, os, n, ar.rest(), st))) return rc;
         for (u32 s = 0; s < n_sum; s++) {
-            const ckks_key* k = sum_keys[s];
-            if ((rc = run_rotate_batch(c, l1, n, ps, &k, true, &g_sum[s], orot, ws, st))) return rc;
+            const ckks_key* ks[CT_BATCH];
+            u32 gs[CT_BATCH];
+            for (u32 b = 0; b < n; b++) {
+                ks[b] = sum_keys[s];
+                gs[b] = g_sum[s];
+            }
+            if ((rc = run_rotate_batch(c, l1, n, ps, ks, gs, orot, ws, st))) return rc;
             for (u32 b = 0; b < n; b++) {
                 const u64* two[2] = {ps[b], orot[b]};
                 HIP_TRY(launch_ct_sum(c, l1, ptr_list(two, 2), 2, os[b], st));
@@ -839,77 +992,14 @@ int he_fc_batched(const ckks_ctx* c, const he_fc_desc* d, const uint64_t* d_in, 
         for (u32 i = 0; i < d->d_out; i++) cts[i] = S + i * ct1;
         if ((rc = run_merge(c, cts, d->d_out, l1, (const u64*)d_merge_mask, merge_keys, g_merge, U, ar.rest(), st))) return rc;
     }
-    // 3. layout.  First rotations (mod_idx = l*delta): hoisted, one decomposition of U
-    {
-        if (!ks_at(l2)) return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for the layer");
-        const u64* uc1 = U + (size_t)(l2 + 1) * N;
-        if ((rc = run_modup(c, l2, &uc1, 1, ws, st))) return rc;
-        HIP_TRY(launch_copy(U, R, ct2, st));
-        for (u32 l0 = 1; l0 < n_lo; l0 += CT_BATCH) {
-            const u32 n = n_lo - l0 < CT_BATCH ? n_lo - l0 : CT_BATCH;
-            FinalItem items[CT_BATCH];
-            u32 nk = 0;
-            for (u32 b = 0; b < n; b++) {
-                if (g_lo[l0 + b] == 1) {  // delta = 0: nothing moves
-                    HIP_TRY(launch_copy(U, R + (l0 + b) * ct2, ct2, st));
-                    continue;
-                }
-                HIP_TRY(launch_key_inner(c, l2, ws.digits, lo_keys[l0 + b]->d_key, g_lo[l0 + b], ws.v + nk * ws.v_b, st));
-                items[nk++] = FinalItem{U, nullptr, nullptr, R + (l0 + b) * ct2, g_lo[l0 + b], 0};
-            }
-            if (nk && (rc = run_moddown(c, l2, ws, nk, items, st))) return rc;
-        }
-    }
-    // masked sums per base block, rescaled
-    const size_t mask_elems = (size_t)(l2 + 1) * N;
-    for (u32 h = 0; h < n_hi; h++) {
-        std::vector<const u64*> pts, cts;
-        for (u32 l = 0; l < n_lo && h * base + l < d->batch; l++) {
-            pts.push_back((const u64*)d_place_masks + (size_t)(h * base + l) * mask_elems);
-            cts.push_back(R + l * ct2);
-        }
-        HIP_TRY(launch_ptct_mac(c, l2, pts.data(), cts.data(), (u32)pts.size(), Vacc + h * ct2, 0, st));
-    }
-    for (u32 h0 = 0; h0 < n_hi; h0 += CT_BATCH) {
-        const u32 n = n_hi - h0 < CT_BATCH ? n_hi - h0 : CT_BATCH;
-        const u64* pv[CT_BATCH];
-        u64* ov[CT_BATCH];
-        for (u32 b = 0; b < n; b++) {
-            pv[b] = Vacc + (h0 + b) * ct2;
-            ov[b] = V + (h0 + b) * ct3;
-        }
-        if ((rc = run_rescale(c, l2, pv, (size_t)(l2 + 1) * N, ov, n, ar.rest(), st))) return rc;
-    }
-    // second rotations (base_idx = h*base*delta), one key each, then the sum
-    if (!ks_at(l3)) return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for the layer");
-    for (u32 h0 = 1; h0 < n_hi; h0 += CT_BATCH) {
-        const u32 n = n_hi - h0 < CT_BATCH ? n_hi - h0 : CT_BATCH;
-        const u64* srcs[CT_BATCH];
-        const ckks_key* ks[CT_BATCH];
-        u32 gs[CT_BATCH];
-        u64* outs[CT_BATCH];
-        u32 nk = 0;
-        for (u32 b = 0; b < n; b++) {
-            if (g_hi[h0 + b] == 1) {
-                HIP_TRY(launch_copy(V + (h0 + b) * ct3, Vrot + (h0 + b) * ct3, ct3, st));
-                continue;
-            }
-            srcs[nk] = V + (h0 + b) * ct3;
-            ks[nk] = hi_keys[h0 + b];
-            gs[nk] = g_hi[h0 + b];
-            outs[nk++] = Vrot + (h0 + b) * ct3;
-        }
-        if (nk && (rc = run_rotate_batch(c, l3, nk, srcs, ks, false, gs, outs, ws, st))) return rc;
-    }
+    // 3. layout: block j moves left by mod_idx = (j % base)*delta, then by base_idx = (j / base)*base*delta
     u64* out = (u64*)d_out;
     {
-        for (u32 h = 0; h < n_hi;) {  // the running sum is one of the terms of every launch after the first
-            const u64* terms[KS_MAX_BATCH];
-            u32 nt = 0;
-            if (h) terms[nt++] = out;
-            for (; h < n_hi && nt < KS_MAX_BATCH; h++) terms[nt++] = h == 0 ? V : Vrot + h * ct3;
-            HIP_TRY(launch_ct_sum(c, l3, ptr_list(terms, nt), nt, out, st));
-        }
+        std::vector<const u64*> masks((size_t)n_hi * n_lo, nullptr);
+        for (u32 j = 0; j < d->batch; j++) masks[(size_t)(j / base) * n_lo + j % base] = (const u64*)d_place_masks + (size_t)j * (l2 + 1) * N;
+        const u64* u_in = U;
+        if ((rc = run_relayout(c, l2, 1, &u_in, n_lo, lo_keys, g_lo.data(), n_hi, hi_keys, g_hi.data(), masks.data(), &out, ar.rest(), st)))
+            return rc;
     }
     // 4. bias on component 0
     HIP_TRY(launch_add_plain(c, l3, (const u64*)d_bias, out, st));

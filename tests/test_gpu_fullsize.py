@@ -216,3 +216,41 @@ def test_fc_batched_at_the_classifier_shape():
     dec = orc.decrypt(got, level - 3, s_ntt, scale)
     assert np.abs(dec[:batch * d_out] - (X @ W.T + bias).reshape(-1)).max() < 1e-4
     assert np.abs(dec[batch * d_out:]).max() < 1e-4
+
+
+def test_downsample_and_merge_at_the_block_group_transition():
+    """Stage 2 -> stage 3 of the batched ResNet-20 at N = 2^16: two channel ciphertexts of 128 images of 16x16 (all N/2
+    slots) are compacted with stride 2 to 8x8 (8192 slots each), residues of both re-layouts against the oracle; four
+    such tiles of one channel (the same ciphertext at four stages of noise would do: here four different ones) are then
+    merged by the accumulator into a ciphertext of 512 images, checked in the slots."""
+    wl = CONFIGS["cfg5_resnet20_stage3"]
+    p = wl.params()
+    orc, ctx = Oracle(p), hx.Context(p)
+    level, height, width, batch, r = 12, 16, 16, 128, 2
+    s, s_ntt = orc.gen_secret(8000)
+    rng = np.random.default_rng(8001)
+    scale = 2.0 ** 40
+    X = rng.uniform(-1, 1, (4, batch, height, width))
+    cts = [orc.encrypt(X[t].reshape(-1), scale, level, s_ntt, 8010 + t) for t in range(4)]
+    plan = orc.downsample_plan(height, width, batch, r)
+    offs = sorted({o for lo, hi, _ in plan for o in list(lo) + list(hi) if o % orc.n})
+    keys = {o: orc.gen_rotation_key(s, s_ntt, o, 8100 + k) for k, o in enumerate(offs)}
+    dkeys = {o: hx.ckks_key_load(ctx, hx.from_host(k), hx.ckks_galois_element(ctx, o)) for o, k in keys.items()}
+    cur = [hx.from_host(ct) for ct in cts]
+    want = cts[:2]
+    for stage, (lo, hi, slot_masks) in enumerate(plan):
+        lv = level - stage
+        enc = [[None if m is None else orc.encode_ntt(m, float(p.moduli[lv]), lv) for m in row] for row in slot_masks]
+        cur = hx.he_relayout_two_rotations(ctx, cur, lv, lo, [dkeys.get(o) for o in lo], hi, [dkeys.get(o) for o in hi],
+                                           [[None if m is None else hx.from_host(m) for m in row] for row in enc])
+        want = [orc.relayout_two_rotations(ct, lv, lo, hi, enc, keys) for ct in want]      # the oracle follows two of the four
+        for b in range(2):
+            assert np.array_equal(hx.to_host(cur[b]), want[b]), f"stage {stage}, ciphertext {b}"
+        del enc
+    lm, sts2 = level - 2, batch * height * width // 4
+    M = orc.encode_ntt(orc.cleaning_mask(sts2), float(p.moduli[lm]), lm)
+    mk = [None] + [hx.ckks_key_load(ctx, hx.from_host(orc.gen_rotation_key(s, s_ntt, -i * sts2, 8200 + i)),
+                                   hx.ckks_galois_element(ctx, -i * sts2)) for i in range(1, 4)]
+    joined = hx.to_host(hx.he_accumulator_merge(ctx, cur, lm, sts2, hx.from_host(M), mk))
+    dec = orc.decrypt(joined, lm - 1, s_ntt, scale)
+    assert np.abs(dec - X[:, :, ::r, ::r].reshape(-1)).max() < 1e-5

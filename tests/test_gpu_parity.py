@@ -381,6 +381,72 @@ def test_fc_batched_rejects_bad_shapes_and_keys():
     assert e.value.code == hx.binding.CKKS_ERR_WORKSPACE_TOO_SMALL
 
 
+# ------------------------------------------------------------------- down-sampling compaction
+def run_downsample(orc, ctx, s, s_ntt, cts, level, plan, seed):
+    """Both stages of the plan on the GPU (channel vector at once) and in the oracle (one by one); returns (got, want)."""
+    offs = sorted({r for lo, hi, _ in plan for r in list(lo) + list(hi) if r % orc.n})
+    keys = {r: orc.gen_rotation_key(s, s_ntt, r, seed + k) for k, r in enumerate(offs)}
+    dkeys = {r: hx.ckks_key_load(ctx, hx.from_host(k), hx.ckks_galois_element(ctx, r)) for r, k in keys.items()}
+    cur = [hx.from_host(ct) for ct in cts]
+    want = [ct for ct in cts]
+    for stage, (lo, hi, slot_masks) in enumerate(plan):
+        lv = level - stage
+        enc = [[None if m is None else orc.encode_ntt(m, float(orc.moduli[lv]), lv) for m in row] for row in slot_masks]
+        cur = hx.he_relayout_two_rotations(ctx, cur, lv, lo, [dkeys.get(r) for r in lo], hi, [dkeys.get(r) for r in hi],
+                                           [[None if m is None else hx.from_host(m) for m in row] for row in enc])
+        want = [orc.relayout_two_rotations(ct, lv, lo, hi, enc, keys) for ct in want]
+        for b in range(len(cts)):
+            assert np.array_equal(hx.to_host(cur[b]), want[b]), f"stage {stage}, ciphertext {b}"
+    return [hx.to_host(t) for t in cur], want
+
+
+@pytest.mark.parametrize("height,width,batch,r,base,n_ct", [(4, 4, 8, 2, 3, 1), (4, 8, 5, 2, 0, 3), (8, 8, 2, 4, 1, 2), (2, 2, 20, 2, 20, 10)])
+def test_downsample_compaction_matches_oracle(height, width, batch, r, base, n_ct):
+    """Stride-r slot compaction of a channel vector: residues of both stages against the oracle, slots against numpy
+    slicing.  One ciphertext (first rotations batched over offsets), three (two offsets per batch), ten (two channel
+    batches; 20 first rotations and a single second one), stride 4, base 1 (only second rotations in stage B)."""
+    p = make_params(10, 5, 2, 3)
+    orc, ctx = both(p)
+    level = p.num_q - 1
+    s, s_ntt = orc.gen_secret(600)
+    rng = np.random.default_rng(601)
+    scale = 2.0 ** 40
+    X = rng.uniform(-1, 1, (n_ct, batch, height, width))
+    cts = []
+    for c in range(n_ct):
+        z = rng.uniform(-1, 1, orc.n)                       # junk behind the images
+        z[:batch * height * width] = X[c].reshape(-1)
+        cts.append(orc.encrypt(z, scale, level, s_ntt, 610 + c))
+    plan = orc.downsample_plan(height, width, batch, r, base)
+    got, _ = run_downsample(orc, ctx, s, s_ntt, cts, level, plan, 650)
+    for c in range(n_ct):
+        dec = orc.decrypt(got[c], level - 2, s_ntt, scale)
+        want = X[c][:, ::r, ::r].reshape(-1)
+        assert np.abs(dec[:want.size] - want).max() < 1e-5 and np.abs(dec[want.size:]).max() < 1e-5
+
+
+def test_relayout_rejects_bad_arguments():
+    p = make_params(10, 5, 2, 3)
+    orc, ctx = both(p)
+    level = 3
+    s, s_ntt = orc.gen_secret(700)
+    key = hx.ckks_key_load(ctx, hx.from_host(orc.gen_rotation_key(s, s_ntt, 4, 701)), hx.ckks_galois_element(ctx, 4))
+    ct, m = hx.empty(2, level + 1, orc.N), hx.empty(level + 1, orc.N)
+    with pytest.raises(hx.CkksError) as e:                  # the key was made for another offset
+        hx.he_relayout_two_rotations(ctx, [ct], level, [0, 5], [None, key], [0], [None], [[m, m]])
+    assert e.value.code == hx.binding.CKKS_ERR_NO_KEY
+    with pytest.raises(hx.CkksError) as e:                  # a second rotation without any mask
+        hx.he_relayout_two_rotations(ctx, [ct], level, [0, 4], [None, key], [0, 4], [None, key], [[m, m], [None, None]])
+    assert e.value.code == hx.binding.CKKS_ERR_INVALID_ARG
+    with pytest.raises(hx.CkksError) as e:                  # level 0 has no limb to drop
+        hx.he_relayout_two_rotations(ctx, [hx.empty(2, 1, orc.N)], 0, [0], [None], [0], [None], [[hx.empty(1, orc.N)]],
+                                     outs=[hx.empty(0)])
+    assert e.value.code == hx.binding.CKKS_ERR_LEVEL_MISMATCH
+    with pytest.raises(hx.CkksError) as e:
+        hx.he_relayout_two_rotations(ctx, [ct], level, [0, 4], [None, key], [0], [None], [[m, m]], ws=hx.empty(512))
+    assert e.value.code == hx.binding.CKKS_ERR_WORKSPACE_TOO_SMALL
+
+
 # ------------------------------------------------------------------------------------ activation
 @pytest.mark.parametrize("n_ct", [1, 3, 10])
 def test_poly_activation_matches_oracle(n_ct):
