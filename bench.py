@@ -330,6 +330,40 @@ def main():
     result["fc_layer_shape"] = {"d_in": fc_in, "d_out": fc_out, "batch": fc_batch, "level": fc_level, "base": fc_base,
                                 "key_switches": sum(k is not None for ks in fc_keys for k in ks) + (fc_out - 1) * 6}
     del fc_keys, fc_ws
+    # down-sampling compaction at the stage-2 -> stage-3 transition: 64 channel ciphertexts of 128 images of 16x16 -> 8x8
+    # (two re-layouts: inside the images 8 + 8 offsets, whole images base 12: 12 + 11), at the level the slice ends on
+    ds_level, ds_n = level - 5, 64
+    stages = [([x for x in range(8)], [y * 24 for y in range(8)]), ([l * 192 for l in range(12)], [h * 12 * 192 for h in range(11)])]
+    ds_in = [hx.empty(2, ds_level + 1, N).copy_(ins[i % len(ins)][:, :ds_level + 1]) for i in range(ds_n)]
+    ds_ws = hx.empty(max(hx.he_relayout_workspace_bytes(ctx, ds_level - k, ds_n, len(lo), len(hi)) for k, (lo, hi) in enumerate(stages)) // 8)
+    ds_args = []
+    for k, (lo, hi) in enumerate(stages):
+        lv = ds_level - k
+        mk = lambda offs, salt: [None if r % (N // 2) == 0 else
+                                 hx.ckks_key_load(ctx, base_keys[(salt + j) % len(base_keys)].tensor.clone(), hx.ckks_galois_element(ctx, r))
+                                 for j, r in enumerate(offs)]
+        n_pairs = len(lo) * len(hi) if k == 0 else 128          # stage B: one pair per image
+        ms = [[(masks[(h * len(lo) + l) % 9, :lv + 1].contiguous() if h * len(lo) + l < n_pairs else None) for l in range(len(lo))]
+              for h in range(len(hi))]
+        ds_args.append((lv, lo, mk(lo, 3 * k), hi, mk(hi, 3 * k + 5), ms, [hx.empty(2, lv, N) for _ in range(ds_n)]))
+
+    def run_ds():
+        cur = ds_in
+        for lv, lo, lk, hi, hk, ms, outs in ds_args:
+            cur = hx.he_relayout_two_rotations(ctx, cur, lv, lo, lk, hi, hk, ms, outs=outs, ws=ds_ws)
+    run_ds()
+    torch.cuda.synchronize()
+    reps = 3
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        run_ds()
+    torch.cuda.synchronize()
+    ds_dt = (time.perf_counter() - t0) / reps
+    result["downsample_ms"] = ds_dt * 1e3
+    result["downsample_ms_per_image"] = ds_dt * 1e3 / 128
+    result["downsample_shape"] = {"channels": ds_n, "from": "16x16", "to": "8x8", "batch": 128, "level": ds_level,
+                                  "key_switches": ds_n * sum(sum(1 for r in lo + hi if r % (N // 2)) for lo, hi in stages)}
+    del ds_args, ds_ws, ds_in
     # NTT microbenchmark: 64 polynomials x 30 limbs at N = 2^16, forward then inverse
     p2 = CONFIGS["cfg2_ntt"].params()
     ctx2 = hx.Context(p2)
