@@ -628,7 +628,9 @@ void orc_lift_ntt(void* h, const i64* coeffs, const int* mod_idx, int n_mod, u64
 // Switching key from s' to s over all num_q+num_p moduli, dnum digits:
 //   a_j uniform, b_j = -a_j s + e_j + F_j s',  F_j = P mod q_i on the digit's own limbs, 0 elsewhere.
 // s_ntt, sp_ntt: [num_q+num_p][N] NTT form.  key: [dnum][2][num_q+num_p][N] with comp 0 = b, 1 = a.
-void orc_gen_switch_key(void* h, const u64* s_ntt, const u64* sp_ntt, u64 seed, u64* key) {
+// a_in: null (a_j drawn from the key's own sequential streams) or [dnum][num_q+num_p][N] given by the caller
+// (the seed-expanded public halves of a staged key).
+void orc_gen_switch_key_with_a(void* h, const u64* s_ntt, const u64* sp_ntt, u64 seed, const u64* a_in, u64* key) {
     Ctx* c = (Ctx*)h;
     int N = c->N, M = c->num_q + c->num_p;
     std::vector<int> all(M);
@@ -645,7 +647,8 @@ void orc_gen_switch_key(void* h, const u64* s_ntt, const u64* sp_ntt, u64 seed, 
             u64 q = c->mod[t];
             u64* b = key + (((size_t)j * 2 + 0) * M + t) * N;
             u64* a = key + (((size_t)j * 2 + 1) * M + t) * N;
-            orc_sample_uniform(seed + 7919ull * ((u64)j * M + t + 1), q, N, a);
+            if (a_in) std::memcpy(a, a_in + ((size_t)j * M + t) * N, (size_t)N * sizeof(u64));
+            else orc_sample_uniform(seed + 7919ull * ((u64)j * M + t + 1), q, N, a);
             u64 F = 0;
             if (t >= lo && t < hi) { F = 1; for (int p = 0; p < c->num_p; p++) F = mulmod(F, c->mod[c->num_q + p] % q, q); }
             for (int x = 0; x < N; x++) {
@@ -655,6 +658,10 @@ void orc_gen_switch_key(void* h, const u64* s_ntt, const u64* sp_ntt, u64 seed, 
             }
         }
     }
+}
+
+void orc_gen_switch_key(void* h, const u64* s_ntt, const u64* sp_ntt, u64 seed, u64* key) {
+    orc_gen_switch_key_with_a(h, s_ntt, sp_ntt, seed, nullptr, key);
 }
 
 // Symmetric encryption of integer coefficients m at `level`: ct = (-a s + m + e, a), NTT form.

@@ -357,6 +357,57 @@ class Oracle:
         sp[e % self.N] = np.where(e < self.N, s, -s)
         return self._gen_switch_key(s_ntt, self.lift_ntt(sp, list(range(self.M))), seed)
 
+    # ---- staged keys: the public half a_j is a function of a 64-bit seed ("Evaluation Keys Reuse": key sets are
+    # offloaded and reloaded between block groups; only b_j and the seed have to be kept and moved)
+    @staticmethod
+    def splitmix64_at(seed: int, index: np.ndarray) -> np.ndarray:
+        """Output number `index` (0-based) of the SplitMix64 sequence started at `seed` (Steele, Lea, Flood 2014):
+        the state advances by the golden-ratio constant, so any output can be computed on its own."""
+        with np.errstate(over="ignore"):
+            z = np.uint64(seed) + (np.asarray(index, dtype=np.uint64) + np.uint64(1)) * np.uint64(0x9E3779B97F4A7C15)
+            z = (z ^ (z >> np.uint64(30))) * np.uint64(0xBF58476D1CE4E5B9)
+            z = (z ^ (z >> np.uint64(27))) * np.uint64(0x94D049BB133111EB)
+            return z ^ (z >> np.uint64(31))
+
+    def expand_key_a(self, a_seed: int) -> np.ndarray:
+        """a[j][t][x], uniform modulo the t-th modulus of the key (q_0..q_L, p_0..), evaluation form: element number
+        e = (j*M + t)*N + x takes the outputs 64 e, 64 e + 1, ... of the sequence; the top bitlength(q) bits of the
+        first one below q are the value (rejection sampling, so the value is exactly uniform; after 64 rejections,
+        probability below 2^-64, the last output is reduced modulo q)."""
+        out = np.empty((self.dnum, self.M, self.N), dtype=np.uint64)
+        x = np.arange(self.N, dtype=np.uint64)
+        for j in range(self.dnum):
+            for t in range(self.M):
+                q = self.moduli[t]
+                shift = np.uint64(64 - q.bit_length())
+                e = np.uint64((j * self.M + t) * self.N) + x
+                val = np.zeros(self.N, dtype=np.uint64)
+                todo = np.ones(self.N, dtype=bool)
+                for attempt in range(64):
+                    z = self.splitmix64_at(a_seed, e[todo] * np.uint64(64) + np.uint64(attempt))
+                    v = z >> shift
+                    ok = v < np.uint64(q)
+                    idx = np.flatnonzero(todo)
+                    val[idx[ok]] = v[ok]
+                    if attempt == 63:
+                        val[idx[~ok]] = z[~ok] % np.uint64(q)
+                    todo[idx[ok]] = False
+                    if not todo.any():
+                        break
+                out[j, t] = val
+        return out
+
+    def gen_rotation_key_seeded(self, s: np.ndarray, s_ntt: np.ndarray, offset: int, seed: int, a_seed: int) -> np.ndarray:
+        """As gen_rotation_key, with the public halves a_j = expand_key_a(a_seed); the errors come from `seed`."""
+        g = self.galois(offset)
+        sp = np.zeros(self.N, dtype=np.int64)
+        e = (np.arange(self.N, dtype=np.int64) * g) % (2 * self.N)
+        sp[e % self.N] = np.where(e < self.N, s, -s)
+        key = np.empty((self.dnum, 2, self.M, self.N), dtype=np.uint64)
+        a = self.expand_key_a(a_seed)
+        self.lib.orc_gen_switch_key_with_a(self.h, _p(_u64(s_ntt)), _p(self.lift_ntt(sp, list(range(self.M)))), C.c_uint64(seed), _p(a), _p(key))
+        return key
+
     def mul(self, a, b, mod_idx: Sequence[int]) -> np.ndarray:
         """a (.) b, limb t modulo moduli[mod_idx[t]]; a, b [len(mod_idx)][N]."""
         a, b = _u64(a), _u64(b)

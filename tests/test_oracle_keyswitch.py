@@ -108,6 +108,87 @@ def test_switch_key_structure(tiny_params):
         assert max(abs(v) for v in errs[0]) <= 19 and any(errs[0])
 
 
+def test_splitmix64_indexed_matches_the_sequential_generator():
+    """The indexed form against the generator stepped one output at a time in Python integers, and against the first
+    outputs for seed 1234567 that implementations of SplitMix64 are commonly checked with."""
+    def sequential(seed, n):
+        out, x, mask = [], seed, (1 << 64) - 1
+        for _ in range(n):
+            x = (x + 0x9E3779B97F4A7C15) & mask
+            z = x
+            z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & mask
+            z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & mask
+            out.append(z ^ (z >> 31))
+        return out
+    for seed in (0, 1234567, (1 << 64) - 5):
+        got = Oracle.splitmix64_at(seed, np.arange(40)).tolist()
+        assert got == sequential(seed, 40)
+    assert Oracle.splitmix64_at(1234567, np.arange(5)).tolist() == [
+        6457827717110365317, 3203168211198807973, 9817491932198370423, 4593380528125082431, 16408922859458223821]
+
+
+def test_expanded_key_halves_are_uniform_residues(tiny_params):
+    """Every value is below its modulus, the first value of a limb is what the definition gives when followed by hand,
+    limbs differ from each other, and the top three bits are flat (chi-square over 8 bins, 7 degrees of freedom)."""
+    p = make_params(10, 4, 2, 2)
+    o = Oracle(p)
+    a = o.expand_key_a(99)
+    assert a.shape == (o.dnum, o.M, o.N)
+    for t in range(o.M):
+        assert int(a[:, t].max()) < p.moduli[t]
+    j, t, x = 1, 3, 17
+    q = p.moduli[t]
+    e = (j * o.M + t) * o.N + x
+    want = None
+    for attempt in range(64):
+        v = int(Oracle.splitmix64_at(99, np.array([64 * e + attempt]))[0]) >> (64 - q.bit_length())
+        if v < q:
+            want = v
+            break
+    assert int(a[j, t, x]) == want
+    assert not np.array_equal(a[0, 0], a[0, 1]) and not np.array_equal(a[0, 0], a[1, 0])
+    assert not np.array_equal(a, o.expand_key_a(100))
+    top = (a.reshape(-1) >> np.uint64(p.moduli[0].bit_length() - 3)).astype(np.int64)
+    counts = np.bincount(top, minlength=8)[:8]
+    expect = a.size / 8
+    assert ((counts - expect) ** 2 / expect).sum() < 30.0
+    # a small modulus makes rejections frequent: values stay exact residues and uniform
+    small = Oracle(make_params(4, 2, 1, 1, bits=12))
+    b = small.expand_key_a(5)
+    assert all(int(b[:, t].max()) < small.moduli[t] for t in range(small.M))
+
+
+def test_seeded_switch_key_has_the_key_structure_and_switches(tiny_params):
+    """b_j + a_j s - F_j sigma_g(s) is a small error with a_j = the expansion of the seed, and a rotation with the seeded
+    key decrypts to the rotated slots."""
+    p = make_params(10, 4, 2, 2)
+    o = Oracle(p)
+    s, s_ntt = o.gen_secret(31)
+    key = o.gen_rotation_key_seeded(s, s_ntt, 3, 32, a_seed=777)
+    assert np.array_equal(key[:, 1], o.expand_key_a(777))
+    g = o.galois(3)
+    sp = np.zeros(o.N, dtype=np.int64)
+    e = (np.arange(o.N, dtype=np.int64) * g) % (2 * o.N)
+    sp[e % o.N] = np.where(e < o.N, s, -s)
+    sp_ntt = o.lift_ntt(sp, list(range(o.M)))
+    P = prod(p.moduli[p.num_q:])
+    for j in range(p.dnum):
+        lo, hi = j * o.alpha, min((j + 1) * o.alpha, p.num_q)
+        for t in (0, o.M - 1, lo):
+            q = p.moduli[t]
+            F = P % q if lo <= t < hi else 0
+            r = [(int(b) + int(a) * int(sv) - F * int(spv)) % q for b, a, sv, spv in zip(key[j, 0, t], key[j, 1, t], s_ntt[t], sp_ntt[t])]
+            err = [centred(int(v), q) for v in o.ntt_inv(np.array(r, dtype=np.uint64), t)]
+            assert max(abs(v) for v in err) <= 19 and any(err)
+    plain = o.gen_rotation_key(s, s_ntt, 3, 32)
+    assert not np.array_equal(key[:, 1], plain[:, 1])
+    z = np.random.default_rng(33).uniform(-1, 1, o.n)
+    level = p.num_q - 1
+    ct = o.encrypt(z, 2.0 ** 40, level, s_ntt, 34)
+    out = o.rotate(ct, level, 3, key, True)
+    assert np.abs(o.decrypt(out, level, s_ntt, 2.0 ** 40) - np.roll(z, -3)).max() < 1e-6
+
+
 def _noise_bound(o, level, sigma=3.2):
     N = o.N
     beta = o.live_digits(level)
