@@ -96,6 +96,21 @@ int ckks_ntt_inv(const ckks_ctx* ctx, uint64_t* d_polys, const uint32_t* h_modul
 int ckks_key_load(const ckks_ctx* ctx, const uint64_t* d_key, uint32_t galois_elt, ckks_key** out_key);
 void ckks_key_free(ckks_key* key);
 
+/* Staged keys ("Optimized Inference Pipeline", Evaluation Keys Reuse: only the keys of the current block group are
+ * resident; sets are offloaded and loaded between groups).  The public halves a_j of a switching key are uniform
+ * residues, so a staged key is its b_j halves (host, uint64[dnum][num_q+num_p][N], evaluation form) plus a 64-bit
+ * seed: a[j][t][x] = the top bitlength(q_t) bits of the first of the outputs 64e, 64e+1, ... (e = (j*M + t)*N + x,
+ * M = num_q+num_p) of the SplitMix64 sequence started at the seed that is below q_t (the 64th output reduced mod
+ * q_t if none is).  Half the bytes cross the host link.
+ * ckks_key_expand_a writes the a halves of d_key (uint64[dnum][2][M][N]); the b halves are left as they are.
+ * ckks_keyset_stage enqueues, for each of n_keys keys, the copy of h_b[i] (pinned host memory for the copy to be
+ * asynchronous) into the b halves of h_d_keys[i] and the expansion of h_a_seeds[i], all on `stream` (normally a
+ * copy stream of the caller's, ordered against the compute stream with the caller's events); no allocation, no
+ * synchronisation.  The device buffers are then keys for ckks_key_load. */
+int ckks_key_expand_a(const ckks_ctx* ctx, uint64_t a_seed, uint64_t* d_key, void* stream);
+int ckks_keyset_stage(const ckks_ctx* ctx, const uint64_t* const* h_b, const uint64_t* h_a_seeds,
+                      uint64_t* const* h_d_keys, uint32_t n_keys, void* stream);
+
 /* Galois element of a left rotation by `offset` slots (negative = right): 5^offset mod 2N. */
 uint32_t ckks_galois_element(const ckks_ctx* ctx, int32_t offset);
 

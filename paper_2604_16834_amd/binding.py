@@ -43,7 +43,7 @@ EXPORTS = (
     "ckks_keyswitch", "ckks_rotate_hoisted", "ckks_ptct_mac", "ckks_rescale", "ckks_ctct_mul_relin",
     "he_conv_workspace_bytes", "he_conv_batched", "he_poly_act_deg7",
     "he_accumulator_workspace_bytes", "he_accumulator_merge", "he_fc_workspace_bytes", "he_fc_batched",
-    "he_relayout_workspace_bytes", "he_relayout_two_rotations",
+    "he_relayout_workspace_bytes", "he_relayout_two_rotations", "ckks_key_expand_a", "ckks_keyset_stage",
     "ckks_prof_kernel_count", "ckks_prof_kernel_name", "ckks_prof_begin", "ckks_prof_end",
 )
 
@@ -109,6 +109,8 @@ def _bind(path: str):
     lib.he_relayout_workspace_bytes.restype = sz
     lib.he_relayout_two_rotations.argtypes = [vp, C.POINTER(vp), u32, u32, C.POINTER(C.c_int32), u32, C.POINTER(vp), C.POINTER(C.c_int32),
                                               u32, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), vp, sz, vp]
+    lib.ckks_key_expand_a.argtypes = [vp, C.c_uint64, vp, vp]
+    lib.ckks_keyset_stage.argtypes = [vp, C.POINTER(vp), C.POINTER(C.c_uint64), C.POINTER(vp), u32, vp]
     lib.ckks_prof_kernel_count.restype = u32
     lib.ckks_prof_kernel_name.argtypes = [u32]
     lib.ckks_prof_kernel_name.restype = C.c_char_p
@@ -179,6 +181,7 @@ class Context:
     def __init__(self, params):
         self.log_n, self.num_q, self.num_p, self.dnum = int(params.log_n), int(params.num_q), int(params.num_p), int(params.dnum)
         self.N = 1 << self.log_n
+        self.M = self.num_q + self.num_p
         self.moduli = [int(q) for q in params.moduli]
         self._mods = (C.c_uint64 * len(self.moduli))(*self.moduli)
         self._psi = (C.c_uint64 * len(self.moduli))(*[int(x) for x in params.psi])
@@ -408,6 +411,30 @@ def he_accumulator_merge(ctx: Context, cts: Sequence[torch.Tensor], level: int, 
     ctx._check(_lib.he_accumulator_merge(ctx.handle, ca, g, level, sts, _ptr(mask), ka, _ptr(out), _ptr(ws),
                                          ws.numel() * ws.element_size(), _stream(stream)))
     return out
+
+
+def ckks_key_expand_a(ctx: Context, a_seed: int, key: torch.Tensor, stream=None) -> torch.Tensor:
+    """Writes the public halves of key ([dnum][2][num_q+num_p][N], device) from the seed; the b halves stay."""
+    if key.numel() != ctx.dnum * 2 * ctx.M * ctx.N:
+        raise ValueError("key must be [dnum][2][num_q+num_p][N]")
+    ctx._check(_lib.ckks_key_expand_a(ctx.handle, C.c_uint64(a_seed), _ptr(key), _stream(stream)))
+    return key
+
+
+def ckks_keyset_stage(ctx: Context, host_b: Sequence[torch.Tensor], a_seeds: Sequence[int], keys: Sequence[torch.Tensor],
+                      stream=None) -> None:
+    """host_b[i]: CPU tensor [dnum][num_q+num_p][N] (pinned for an asynchronous copy); keys[i]: device [dnum][2][M][N]."""
+    n = len(keys)
+    if len(host_b) != n or len(a_seeds) != n:
+        raise ValueError("one host tensor and one seed per key")
+    for hb, k in zip(host_b, keys):
+        if hb.device.type != "cpu" or not hb.is_contiguous() or hb.numel() != ctx.dnum * ctx.M * ctx.N or hb.element_size() != 8:
+            raise ValueError("host_b must be contiguous 64-bit CPU tensors [dnum][num_q+num_p][N]")
+        if k.numel() != ctx.dnum * 2 * ctx.M * ctx.N:
+            raise ValueError("keys must be [dnum][2][num_q+num_p][N]")
+    hb_arr = (C.c_void_p * n)(*[t.data_ptr() for t in host_b])
+    seeds = (C.c_uint64 * n)(*[int(v) for v in a_seeds])
+    ctx._check(_lib.ckks_keyset_stage(ctx.handle, hb_arr, seeds, _ptr_array([_ptr(k) for k in keys]), n, _stream(stream)))
 
 
 def he_relayout_workspace_bytes(ctx: Context, level: int, n_ct: int, n_lo: int, n_hi: int) -> int:

@@ -7,7 +7,7 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 OUT = os.path.join(_HERE, "libckks_mi355x.so")
-SOURCES = ["ntt.hip", "keyswitch.hip", "pointwise.hip", "wsum_mfma.hip", "context.cpp", "api.cpp"]
+SOURCES = ["ntt.hip", "keyswitch.hip", "pointwise.hip", "wsum_mfma.hip", "keystage.hip", "context.cpp", "api.cpp"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # keep the compiler from forming packed-fp32 instructions (no float math on this path anyway)

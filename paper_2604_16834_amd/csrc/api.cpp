@@ -565,6 +565,31 @@ int ckks_key_load(const ckks_ctx* c, const uint64_t* d_key, uint32_t galois_elt,
 }
 void ckks_key_free(ckks_key* k) { delete k; }
 
+int ckks_key_expand_a(const ckks_ctx* c, uint64_t a_seed, uint64_t* d_key, void* stream) {
+    if (!c) return CKKS_ERR_INVALID_ARG;
+    if (!d_key) return set_err(c, CKKS_ERR_INVALID_ARG, "null pointer");
+    if (!c->dnum) return set_err(c, CKKS_ERR_UNSUPPORTED_PARAMS, "context has no key-switching digits");
+    HIP_TRY(launch_key_expand_a(c, a_seed, (u64*)d_key, (hipStream_t)stream));
+    return CKKS_OK;
+}
+
+int ckks_keyset_stage(const ckks_ctx* c, const uint64_t* const* h_b, const uint64_t* h_a_seeds, uint64_t* const* h_d_keys,
+                      uint32_t n_keys, void* stream) {
+    if (!c) return CKKS_ERR_INVALID_ARG;
+    if (!h_b || !h_a_seeds || !h_d_keys) return set_err(c, CKKS_ERR_INVALID_ARG, "null pointer");
+    if (!c->dnum) return set_err(c, CKKS_ERR_UNSUPPORTED_PARAMS, "context has no key-switching digits");
+    for (u32 i = 0; i < n_keys; i++)
+        if (!h_b[i] || !h_d_keys[i]) return set_err(c, CKKS_ERR_INVALID_ARG, "null key pointer");
+    const size_t half = (size_t)c->M * c->N * sizeof(u64);  // one digit's b (or a) part
+    hipStream_t st = (hipStream_t)stream;
+    for (u32 i = 0; i < n_keys; i++) {
+        // the b halves: dnum rows of `half` bytes, densely packed on the host, every other row of the device key
+        HIP_TRY(hipMemcpy2DAsync(h_d_keys[i], 2 * half, h_b[i], half, half, c->dnum, hipMemcpyHostToDevice, st));
+        HIP_TRY(launch_key_expand_a(c, h_a_seeds[i], (u64*)h_d_keys[i], st));
+    }
+    return CKKS_OK;
+}
+
 int ckks_keyswitch(const ckks_ctx* c, const uint64_t* d_c, uint32_t level, const ckks_key* key, uint64_t* d_out, void* d_ws,
                    size_t ws_bytes, void* stream) {
     if (!c) return CKKS_ERR_INVALID_ARG;

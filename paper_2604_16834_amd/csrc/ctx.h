@@ -193,6 +193,7 @@ hipError_t launch_rescale_final(const ckks_ctx* c, u32 level, const PtrList8& ct
 hipError_t launch_tensor(const ckks_ctx* c, u32 level, const PtrList8& a, size_t a_cstride, const PtrList8& b, size_t b_cstride,
                          u64* d0, u64* d1, u64* d2, u32 n, const u64* add, size_t add_bstride, hipStream_t st);
 hipError_t launch_mask_mul(const ckks_ctx* c, u32 level, const u64* mask, const u64* ct, u64* out, hipStream_t st);
+hipError_t launch_key_expand_a(const ckks_ctx* c, u64 seed, u64* key, hipStream_t st);
 hipError_t launch_add_plain(const ckks_ctx* c, u32 level, const u64* pt, u64* ct, hipStream_t st);
 hipError_t launch_ct_sum(const ckks_ctx* c, u32 level, const PtrList8& items, u32 n, u64* out, hipStream_t st);
 hipError_t launch_centre_ext(const ckks_ctx* c, u32 level, const u64* mask, const u64* ct, u64* xs, XLayout xl, u32 k, hipStream_t st);

@@ -381,6 +381,49 @@ def test_fc_batched_rejects_bad_shapes_and_keys():
     assert e.value.code == hx.binding.CKKS_ERR_WORKSPACE_TOO_SMALL
 
 
+# --------------------------------------------------------------------------------- staged keys
+@pytest.mark.parametrize("log_n,num_q,num_p,dnum,bits", [(12, 4, 2, 2, 50), (10, 3, 1, 3, 57), (5, 3, 1, 2, 12)])
+def test_key_expansion_matches_oracle(log_n, num_q, num_p, dnum, bits):
+    """The public halves written on the device from a seed equal the oracle's expansion; the b halves are not touched.
+    50- and 57-bit moduli, and 12-bit ones where rejections are frequent."""
+    p = make_params(log_n, num_q, num_p, dnum, bits=bits)
+    orc, ctx = both(p)
+    rng = np.random.default_rng(800)
+    key = rng.integers(0, 1 << 40, (dnum, 2, orc.M, orc.N), dtype=np.uint64)
+    for seed in (0, 777, (1 << 64) - 3):
+        d = hx.ckks_key_expand_a(ctx, seed, hx.from_host(key))
+        got = hx.to_host(d).reshape(key.shape)
+        assert np.array_equal(got[:, 1], orc.expand_key_a(seed))
+        assert np.array_equal(got[:, 0], key[:, 0])
+
+
+def test_staged_keys_equal_the_oracle_keys_and_rotate():
+    """Two seeded rotation keys staged from pinned host memory on a side stream (b halves copied, a halves expanded):
+    the device keys equal the oracle's keys word for word and a hoisted rotation with them matches the oracle."""
+    import torch
+    p = CONFIGS["small_rotations"].params()
+    orc, ctx = both(p)
+    s, s_ntt = orc.gen_secret(810)
+    offs, seeds = [5, -3], [9001, 9002]
+    keys = [orc.gen_rotation_key_seeded(s, s_ntt, r, 811 + i, a_seed=seeds[i]) for i, r in enumerate(offs)]
+    host_b = [torch.from_numpy(np.ascontiguousarray(k[:, 0]).view(np.int64)).pin_memory() for k in keys]
+    dev = [hx.empty(p.dnum, 2, orc.M, orc.N).fill_(-1) for _ in keys]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())           # the fill above runs on the current stream
+    hx.ckks_keyset_stage(ctx, host_b, seeds, dev, stream=side.cuda_stream)
+    torch.cuda.current_stream().wait_stream(side)
+    for k, d in zip(keys, dev):
+        assert np.array_equal(hx.to_host(d).reshape(k.shape), k)
+    level = p.num_q - 1
+    ct = rand_ct(np.random.default_rng(812), p.moduli, level, orc.N)
+    dk = [hx.ckks_key_load(ctx, d, hx.ckks_galois_element(ctx, r)) for d, r in zip(dev, offs)]
+    outs = hx.ckks_rotate_hoisted(ctx, hx.from_host(ct), level, offs, dk, hoisted=True)
+    for o, w in zip(outs, orc.rotate_many(ct, level, offs, keys, True)):
+        assert np.array_equal(hx.to_host(o), w)
+    with pytest.raises(ValueError):
+        hx.ckks_keyset_stage(ctx, host_b[:1], seeds, dev)
+
+
 # ------------------------------------------------------------------- down-sampling compaction
 def run_downsample(orc, ctx, s, s_ntt, cts, level, plan, seed):
     """Both stages of the plan on the GPU (channel vector at once) and in the oracle (one by one); returns (got, want)."""
