@@ -364,6 +364,36 @@ def main():
     result["downsample_shape"] = {"channels": ds_n, "from": "16x16", "to": "8x8", "batch": 128, "level": ds_level,
                                   "key_switches": ds_n * sum(sum(1 for r in lo + hi if r % (N // 2)) for lo, hi in stages)}
     del ds_args, ds_ws, ds_in
+    # key staging: the block group's 9 keys (8 rotations + relinearisation) as b halves in pinned host memory (48 MiB
+    # each) + seeds, copied and expanded on a side stream, alone and while the block slice runs on the main stream
+    n_stage = 9
+    host_b = [torch.empty(params.dnum, params.num_q + params.num_p, N, dtype=torch.int64).pin_memory() for _ in range(n_stage)]
+    for i, t in enumerate(host_b):
+        t.copy_(base_keys[i % len(base_keys)].tensor.view(params.dnum, 2, -1, N)[:, 0])
+    staged = [hx.empty(params.dnum, 2, params.num_q + params.num_p, N) for _ in range(n_stage)]
+    side = torch.cuda.Stream()
+    stage_bytes = sum(t.numel() * 8 for t in host_b)
+
+    def stage_once():
+        side.wait_stream(torch.cuda.current_stream())
+        hx.ckks_keyset_stage(ctx, host_b, list(range(100, 100 + n_stage)), staged, stream=side.cuda_stream)
+    stage_once()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    stage_once()
+    torch.cuda.synchronize()
+    alone = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    stage_once()
+    for _ in range(2):               # two block-slice steps on the main stream while the side stream stages
+        step()
+    torch.cuda.synchronize()
+    both_dt = time.perf_counter() - t0
+    result["key_staging"] = {"keys": n_stage, "host_bytes": stage_bytes, "device_key_bytes": 2 * stage_bytes,
+                             "ms_alone": alone * 1e3, "host_link_GBs": stage_bytes / alone / 1e9,
+                             "ms_two_steps_while_staging": both_dt * 1e3, "ms_two_steps": 2 * ms_per_step,
+                             "staging_ms_hidden": alone * 1e3 + 2 * ms_per_step - both_dt * 1e3}
+    del host_b, staged
     # NTT microbenchmark: 64 polynomials x 30 limbs at N = 2^16, forward then inverse
     p2 = CONFIGS["cfg2_ntt"].params()
     ctx2 = hx.Context(p2)
