@@ -240,117 +240,171 @@ __device__ __forceinline__ PolyRef<A> poly_ref(const NttArgs& args, const PolyLi
 //   round B: thread = (d3, pos % 32),      points over d2          (distances 128, 64, 32)
 //   round C: thread = (d3, d2, d0),        points over d1          (distances 16, 8, 4)
 //   round D: thread = pos / 8,             8 consecutive points    (distances 2, 1)
+// A workgroup transforms the same (limb, block) slice of IT consecutive batch items one after the other: the
+// slice's twiddles (as many bytes as the tile itself) are fetched once for all of them, and the next item's
+// points are requested before the current item's butterflies start, so their latency hides behind a whole
+// tile of work.  A buffer is rewritten only after a barrier that every reader of its old contents has passed: the
+// forward pass has four exchanges per item (the last one turns each thread's 8 consecutive results into stores of
+// 512 contiguous bytes per wave) and uses the two buffers in turn; the inverse pass has three, so its buffers swap
+// roles from one item to the next.
 template <class A>
-__global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_kernel(NttArgs args, PolyList pl) {
-    typedef typename A::E E;
-    __shared__ E buf0[LDS_PADDED_WORDS];
-    __shared__ E buf1[LDS_PADDED_WORDS];
-    const u32 tid = threadIdx.x;
-    const LoTile tile = lo_tile(args.log_hi, args.lo_group);
-    const u32 blk = tile.blk;
-    const PolyRef<A> P = poly_ref<A>(args, pl, tile.b, tile.a);
-    const u64* src = P.src + ((size_t)blk << 11);
-    u64* dst = P.dst + ((size_t)blk << 11);
-    const u32 TA = (1u << args.log_hi) + blk;
-    const u32 d3 = tid >> 5, x5 = tid & 31, d2 = (tid >> 2) & 7, d0 = tid & 3;
-    typedef typename A::TW TW;
-    E v[8];
-    TW wa[7], wb[7], wc[7], wd[6];
-    load_tw<A, 3>(P.tw, TA, wa);
-    load_tw<A, 3>(P.tw, 8 * TA + d3, wb);
-    if (args.first) {
-#pragma unroll
-        for (int j = 0; j < 8; j++) v[j] = A::load_first(src[tid + 256 * j], P.mc, false);
-    } else {
-#pragma unroll
-        for (int j = 0; j < 8; j++) v[j] = A::load_mid(src[tid + 256 * j]);
-    }
-    fwd_rows_pre<A, 3>(v, wa, P.mc);
-    A::fwd_round_end(v, P.mc);
-    load_tw<A, 3>(P.tw, 64 * TA + 8 * d3 + d2, wc);
-#pragma unroll
-    for (int j = 0; j < 8; j++) buf0[LDS_PAD(tid + 256 * j)] = v[j];
-    __syncthreads();
-#pragma unroll
-    for (int j = 0; j < 8; j++) v[j] = buf0[LDS_PAD(d3 * 256 + 32 * j + x5)];
-    fwd_rows_pre<A, 3>(v, wb, P.mc);
-    A::fwd_round_end(v, P.mc);
-    load_tw<A, 2>(P.tw, 512 * TA + 2 * tid, wd);
-    load_tw<A, 2>(P.tw, 512 * TA + 2 * tid + 1, wd + 3);
-#pragma unroll
-    for (int j = 0; j < 8; j++) buf1[LDS_PAD(d3 * 256 + 32 * j + x5)] = v[j];
-    __syncthreads();
-#pragma unroll
-    for (int j = 0; j < 8; j++) v[j] = buf1[LDS_PAD(d3 * 256 + d2 * 32 + 4 * j + d0)];
-    fwd_rows_pre<A, 3>(v, wc, P.mc);
-    A::fwd_round_end(v, P.mc);
-#pragma unroll
-    for (int j = 0; j < 8; j++) buf0[LDS_PAD(d3 * 256 + d2 * 32 + 4 * j + d0)] = v[j];
-    __syncthreads();
-#pragma unroll
-    for (int j = 0; j < 8; j++) v[j] = buf0[LDS_PAD(8 * tid + j)];
-    fwd_rows_pre<A, 2>(v, wd, P.mc);
-    fwd_rows_pre<A, 2>(v + 4, wd + 3, P.mc);
-    A::fwd_round_end(v, P.mc);
-    ulonglong2* out = reinterpret_cast<ulonglong2*>(dst + 8 * tid);
-#pragma unroll
-    for (int j = 0; j < 4; j++) out[j] = make_ulonglong2(A::store_fwd_final(v[2 * j], P.mc), A::store_fwd_final(v[2 * j + 1], P.mc));
+__device__ __forceinline__ const u64* item_src(const NttArgs& args, const PolyList& pl, u32 b, u32 a) {
+    return (args.use_src_list ? args.src_list.p[b] : args.src + (((size_t)b * args.src_bstride) << args.log_n)) + ((size_t)pl.spos[a] << args.log_n);
+}
+__device__ __forceinline__ u64* item_dst(const NttArgs& args, const PolyList& pl, u32 b, u32 a) {
+    return args.dst + (((size_t)b * args.dst_bstride + pl.dpos[a]) << args.log_n);
 }
 
-template <class A>
-__global__ __launch_bounds__(NTT_THREADS) void ntt_inv_lo_kernel(NttArgs args, PolyList pl) {
+template <class A, int IT>
+__global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_kernel(NttArgs args, PolyList pl) {
     typedef typename A::E E;
-    __shared__ E buf0[LDS_PADDED_WORDS];
-    __shared__ E buf1[LDS_PADDED_WORDS];
+    __shared__ E lds0[LDS_PADDED_WORDS];
+    __shared__ E lds1[LDS_PADDED_WORDS];
     const u32 tid = threadIdx.x;
     const LoTile tile = lo_tile(args.log_hi, args.lo_group);
-    const u32 blk = tile.blk;
-    const PolyRef<A> P = poly_ref<A>(args, pl, tile.b, tile.a);
-    const u64* src = P.src + ((size_t)blk << 11);
-    u64* dst = P.dst + ((size_t)blk << 11);
+    const u32 blk = tile.blk, b0 = tile.b * IT;
+    const u32 cnt = args.batch - b0 < (u32)IT ? args.batch - b0 : (u32)IT;
+    const PolyRef<A> P = poly_ref<A>(args, pl, b0, tile.a);
+    const size_t off = (size_t)blk << 11;
     const u32 TA = (1u << args.log_hi) + blk;
     const u32 d3 = tid >> 5, x5 = tid & 31, d2 = (tid >> 2) & 7, d0 = tid & 3;
     typedef typename A::TW TW;
     E v[8];
+    u64 raw[8];
+    TW wa[7], wb[7], wc[7], wd[6];
+    load_tw<A, 3>(P.tw, TA, wa);
+    load_tw<A, 3>(P.tw, 8 * TA + d3, wb);
+    {
+        const u64* src = P.src + off;
+#pragma unroll
+        for (int j = 0; j < 8; j++) raw[j] = src[tid + 256 * j];
+    }
+#pragma unroll
+    for (int it = 0; it < IT; it++) {
+        if ((u32)it >= cnt) break;
+        E* buf0 = lds0;
+        E* buf1 = lds1;
+        if (args.first) {
+#pragma unroll
+            for (int j = 0; j < 8; j++) v[j] = A::load_first(raw[j], P.mc, false);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; j++) v[j] = A::load_mid(raw[j]);
+        }
+        if (it + 1 < IT && (u32)(it + 1) < cnt) {  // the next item's points, a tile ahead
+            const u64* src = item_src<A>(args, pl, b0 + it + 1, tile.a) + off;
+#pragma unroll
+            for (int j = 0; j < 8; j++) raw[j] = src[tid + 256 * j];
+        }
+        fwd_rows_pre<A, 3>(v, wa, P.mc);
+        A::fwd_round_end(v, P.mc);
+        if (it == 0) load_tw<A, 3>(P.tw, 64 * TA + 8 * d3 + d2, wc);
+#pragma unroll
+        for (int j = 0; j < 8; j++) buf0[LDS_PAD(tid + 256 * j)] = v[j];
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 8; j++) v[j] = buf0[LDS_PAD(d3 * 256 + 32 * j + x5)];
+        fwd_rows_pre<A, 3>(v, wb, P.mc);
+        A::fwd_round_end(v, P.mc);
+        if (it == 0) {
+            load_tw<A, 2>(P.tw, 512 * TA + 2 * tid, wd);
+            load_tw<A, 2>(P.tw, 512 * TA + 2 * tid + 1, wd + 3);
+        }
+#pragma unroll
+        for (int j = 0; j < 8; j++) buf1[LDS_PAD(d3 * 256 + 32 * j + x5)] = v[j];
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 8; j++) v[j] = buf1[LDS_PAD(d3 * 256 + d2 * 32 + 4 * j + d0)];
+        fwd_rows_pre<A, 3>(v, wc, P.mc);
+        A::fwd_round_end(v, P.mc);
+#pragma unroll
+        for (int j = 0; j < 8; j++) buf0[LDS_PAD(d3 * 256 + d2 * 32 + 4 * j + d0)] = v[j];
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 8; j++) v[j] = buf0[LDS_PAD(8 * tid + j)];
+        fwd_rows_pre<A, 2>(v, wd, P.mc);
+        fwd_rows_pre<A, 2>(v + 4, wd + 3, P.mc);
+        A::fwd_round_end(v, P.mc);
+        // back through LDS so that a wave stores 512 contiguous bytes per instruction
+#pragma unroll
+        for (int j = 0; j < 8; j++) buf1[LDS_PAD(8 * tid + j)] = v[j];
+        __syncthreads();
+        u64* dst = item_dst(args, pl, b0 + it, tile.a) + off;
+#pragma unroll
+        for (int j = 0; j < 8; j++) dst[tid + 256 * j] = A::store_fwd_final(buf1[LDS_PAD(tid + 256 * j)], P.mc);
+    }
+}
+
+template <class A, int IT>
+__global__ __launch_bounds__(NTT_THREADS) void ntt_inv_lo_kernel(NttArgs args, PolyList pl) {
+    typedef typename A::E E;
+    __shared__ E lds0[LDS_PADDED_WORDS];
+    __shared__ E lds1[LDS_PADDED_WORDS];
+    const u32 tid = threadIdx.x;
+    const LoTile tile = lo_tile(args.log_hi, args.lo_group);
+    const u32 blk = tile.blk, b0 = tile.b * IT;
+    const u32 cnt = args.batch - b0 < (u32)IT ? args.batch - b0 : (u32)IT;
+    const PolyRef<A> P = poly_ref<A>(args, pl, b0, tile.a);
+    const size_t off = (size_t)blk << 11;
+    const u32 TA = (1u << args.log_hi) + blk;
+    const u32 d3 = tid >> 5, x5 = tid & 31, d2 = (tid >> 2) & 7, d0 = tid & 3;
+    typedef typename A::TW TW;
+    E v[8];
+    ulonglong2 raw[4];
     TW wa[7], wb[7], wc[7], wd[6];
     load_tw<A, 2>(P.tw, 512 * TA + 2 * tid, wd);
     load_tw<A, 2>(P.tw, 512 * TA + 2 * tid + 1, wd + 3);
     load_tw<A, 3>(P.tw, 64 * TA + 8 * d3 + d2, wc);
-    const ulonglong2* in = reinterpret_cast<const ulonglong2*>(src + 8 * tid);
+    {
+        const ulonglong2* in = reinterpret_cast<const ulonglong2*>(P.src + off + 8 * tid);
 #pragma unroll
-    for (int j = 0; j < 4; j++) {
-        const ulonglong2 t = in[j];
-        v[2 * j] = A::load_first(t.x, P.mc, true);
-        v[2 * j + 1] = A::load_first(t.y, P.mc, true);
+        for (int j = 0; j < 4; j++) raw[j] = in[j];
     }
-    inv_rows_pre<A, 2>(v, wd, P.mc);
-    inv_rows_pre<A, 2>(v + 4, wd + 3, P.mc);
-    load_tw<A, 3>(P.tw, 8 * TA + d3, wb);
 #pragma unroll
-    for (int j = 0; j < 8; j++) buf0[LDS_PAD(8 * tid + j)] = v[j];
-    __syncthreads();
+    for (int it = 0; it < IT; it++) {
+        if ((u32)it >= cnt) break;
+        E* buf0 = (it & 1) ? lds1 : lds0;  // three exchanges per item: the buffers swap roles from item to item
+        E* buf1 = (it & 1) ? lds0 : lds1;
 #pragma unroll
-    for (int j = 0; j < 8; j++) v[j] = buf0[LDS_PAD(d3 * 256 + d2 * 32 + 4 * j + d0)];
-    inv_rows_pre<A, 3>(v, wc, P.mc);
-    load_tw<A, 3>(P.tw, TA, wa);
+        for (int j = 0; j < 4; j++) {
+            v[2 * j] = A::load_first(raw[j].x, P.mc, true);
+            v[2 * j + 1] = A::load_first(raw[j].y, P.mc, true);
+        }
+        if (it + 1 < IT && (u32)(it + 1) < cnt) {  // the next item's points, a tile ahead
+            const ulonglong2* in = reinterpret_cast<const ulonglong2*>(item_src<A>(args, pl, b0 + it + 1, tile.a) + off + 8 * tid);
 #pragma unroll
-    for (int j = 0; j < 8; j++) buf1[LDS_PAD(d3 * 256 + d2 * 32 + 4 * j + d0)] = v[j];
-    __syncthreads();
+            for (int j = 0; j < 4; j++) raw[j] = in[j];
+        }
+        inv_rows_pre<A, 2>(v, wd, P.mc);
+        inv_rows_pre<A, 2>(v + 4, wd + 3, P.mc);
+        if (it == 0) load_tw<A, 3>(P.tw, 8 * TA + d3, wb);
 #pragma unroll
-    for (int j = 0; j < 8; j++) v[j] = buf1[LDS_PAD(d3 * 256 + 32 * j + x5)];
-    inv_rows_pre<A, 3>(v, wb, P.mc);
+        for (int j = 0; j < 8; j++) buf0[LDS_PAD(8 * tid + j)] = v[j];
+        __syncthreads();
 #pragma unroll
-    for (int j = 0; j < 8; j++) buf0[LDS_PAD(d3 * 256 + 32 * j + x5)] = v[j];
-    __syncthreads();
+        for (int j = 0; j < 8; j++) v[j] = buf0[LDS_PAD(d3 * 256 + d2 * 32 + 4 * j + d0)];
+        inv_rows_pre<A, 3>(v, wc, P.mc);
+        if (it == 0) load_tw<A, 3>(P.tw, TA, wa);
 #pragma unroll
-    for (int j = 0; j < 8; j++) v[j] = buf0[LDS_PAD(tid + 256 * j)];
-    inv_rows_pre<A, 3>(v, wa, P.mc);
-    if (args.last) {
+        for (int j = 0; j < 8; j++) buf1[LDS_PAD(d3 * 256 + d2 * 32 + 4 * j + d0)] = v[j];
+        __syncthreads();
 #pragma unroll
-        for (int j = 0; j < 8; j++) dst[tid + 256 * j] = A::store_inv_final(v[j], P.mc);
-    } else {
+        for (int j = 0; j < 8; j++) v[j] = buf1[LDS_PAD(d3 * 256 + 32 * j + x5)];
+        inv_rows_pre<A, 3>(v, wb, P.mc);
 #pragma unroll
-        for (int j = 0; j < 8; j++) dst[tid + 256 * j] = A::store_mid(v[j]);  // the hi pass follows
+        for (int j = 0; j < 8; j++) buf0[LDS_PAD(d3 * 256 + 32 * j + x5)] = v[j];
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 8; j++) v[j] = buf0[LDS_PAD(tid + 256 * j)];
+        inv_rows_pre<A, 3>(v, wa, P.mc);
+        u64* dst = item_dst(args, pl, b0 + it, tile.a) + off;
+        if (args.last) {
+#pragma unroll
+            for (int j = 0; j < 8; j++) dst[tid + 256 * j] = A::store_inv_final(v[j], P.mc);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; j++) dst[tid + 256 * j] = A::store_mid(v[j]);  // the hi pass follows
+        }
     }
 }
 
@@ -493,10 +547,15 @@ static void launch_hi_any(u32 log_hi, bool inverse, dim3 grid, hipStream_t st, c
     }
 }
 
+template <class A, int IT>
+static void launch_lo_it(bool inverse, dim3 grid, hipStream_t st, const NttArgs& args, const PolyList& pl) {
+    if (inverse) hipLaunchKernelGGL((ntt_inv_lo_kernel<A, IT>), grid, dim3(NTT_THREADS), 0, st, args, pl);
+    else hipLaunchKernelGGL((ntt_fwd_lo_kernel<A, IT>), grid, dim3(NTT_THREADS), 0, st, args, pl);
+}
 template <class A>
-static void launch_lo(bool inverse, dim3 grid, hipStream_t st, const NttArgs& args, const PolyList& pl) {
-    if (inverse) hipLaunchKernelGGL((ntt_inv_lo_kernel<A>), grid, dim3(NTT_THREADS), 0, st, args, pl);
-    else hipLaunchKernelGGL((ntt_fwd_lo_kernel<A>), grid, dim3(NTT_THREADS), 0, st, args, pl);
+static void launch_lo(bool inverse, u32 items, dim3 grid, hipStream_t st, const NttArgs& args, const PolyList& pl) {
+    if (items == 2) launch_lo_it<A, 2>(inverse, grid, st, args, pl);
+    else launch_lo_it<A, 1>(inverse, grid, st, args, pl);
 }
 
 hipError_t launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, size_t src_bstride, u64* dst,
@@ -536,7 +595,10 @@ hipError_t launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, size_t sr
     }
     const dim3 grid(c->N >> CKKS_TILE_LOG, polys);  // hi pass: one workgroup per 2^11 points
     const u32 slices = pl.n << c->log_hi;
-    const dim3 grid_lo = args.lo_group ? dim3(args.lo_group, batch, slices / args.lo_group) : dim3(batch, slices);  // see lo_tile()
+    // batch items per lo-pass workgroup: two share one fetch of the twiddles (four cost too many registers)
+    const u32 lo_items = batch >= 2 ? 2 : 1;
+    const u32 lo_wgs = (batch + lo_items - 1) / lo_items;
+    const dim3 grid_lo = args.lo_group ? dim3(args.lo_group, lo_wgs, slices / args.lo_group) : dim3(lo_wgs, slices);  // see lo_tile()
     const double lo_ops = 0.5 * polys * c->N * c->log_lo, hi_ops = 0.5 * polys * c->N * c->log_hi;
     // the second pass of either direction continues in place on dst
     NttArgs second = args;
@@ -547,7 +609,7 @@ hipError_t launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, size_t sr
     PolyList pd = pl;
     for (u32 i = 0; i < pl.n; i++) pd.spos[i] = pl.dpos[i];
     auto hi = [&](const NttArgs& a, const PolyList& l) { if (f64) launch_hi_any<ArithF64>(c->log_hi, inverse, grid, st, a, l); else launch_hi_any<ArithU64>(c->log_hi, inverse, grid, st, a, l); };
-    auto lo = [&](const NttArgs& a, const PolyList& l) { if (f64) launch_lo<ArithF64>(inverse, grid_lo, st, a, l); else launch_lo<ArithU64>(inverse, grid_lo, st, a, l); };
+    auto lo = [&](const NttArgs& a, const PolyList& l) { if (f64) launch_lo<ArithF64>(inverse, lo_items, grid_lo, st, a, l); else launch_lo<ArithU64>(inverse, lo_items, grid_lo, st, a, l); };
     if (!inverse) {
         if (c->log_hi > 0) {
             args.last = 0;
