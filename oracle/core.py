@@ -556,24 +556,33 @@ class Oracle:
             X_r = (P * sigma_g(c0) + v_0,  v_1),   v = < sigma_g(ModUp(c1)), key_g >,
         so that ModDown(X_r) = Rot(ct, r); the centre tap is P * ct (zero on the special primes)."""
         ct = _u64(ct)
-        L1, E = level + 1, level + 1 + self.num_p
         digits = self.modup(ct[1], level)
+        return [self.aligned_ext(ct, level, dy * width + dx, rot_keys.get(dy * width + dx), digits) for dy in (-1, 0, 1) for dx in (-1, 0, 1)]
+
+    def aligned_ext(self, ct, level: int, off: int, key, digits) -> np.ndarray:
+        """X = (P * sigma_g(c0) + v_0, v_1) on the extended basis Q_level P, v = < sigma_g(digits), key >, g = 5^off:
+        Rot(ct, off) before its division by P.  off = 0: P * ct.  digits = ModUp(ct[1])."""
+        ct = _u64(ct)
+        L1, E = level + 1, level + 1 + self.num_p
         Pres = self.special_product_residues(level)
-        row = []
-        for dy in (-1, 0, 1):
-            for dx in (-1, 0, 1):
-                off = dy * width + dx
-                x = np.zeros((2, E, self.N), dtype=np.uint64)
-                if off % self.n == 0:
-                    x[:, :L1] = self.scalar_mul(ct, Pres[:L1], level)
-                else:
-                    g = self.galois(off)
-                    v = self.key_inner(self.automorph_ntt(digits, g), rot_keys[off], level)
-                    pc0 = self.scalar_mul(self.automorph_ntt(ct[0], g), Pres[:L1], level)
-                    x[:] = v
-                    x[0, :L1] = self.add(v[0, :L1], pc0, level)
-                row.append(x)
-        return row
+        x = np.zeros((2, E, self.N), dtype=np.uint64)
+        if off % self.n == 0:
+            x[:, :L1] = self.scalar_mul(ct, Pres[:L1], level)
+        else:
+            g = self.galois(off)
+            v = self.key_inner(self.automorph_ntt(digits, g), key, level)
+            pc0 = self.scalar_mul(self.automorph_ntt(ct[0], g), Pres[:L1], level)
+            x[:] = v
+            x[0, :L1] = self.add(v[0, :L1], pc0, level)
+        return x
+
+    def add_ext(self, a, b, level: int) -> np.ndarray:
+        """a + b on the extended basis Q_level P, [..., level+1+k, N]."""
+        a, b = _u64(a), _u64(b)
+        out = np.empty_like(a)
+        for e, t in enumerate(self.ext_moduli_idx(level)):
+            out[..., e, :] = (a[..., e, :] + b[..., e, :]) % np.uint64(self.moduli[t])
+        return out
 
     def he_conv_deferred(self, cts: Sequence[np.ndarray], level: int, width: int, rot_keys: Dict[int, np.ndarray],
                          M_ext: np.ndarray, w_int: np.ndarray, out_channels: Optional[Iterable[int]] = None,
@@ -669,28 +678,54 @@ class Oracle:
             out = V if out is None else self.add(out, V, level - 1)
         return out
 
-    def downsample_plan(self, height: int, width: int, batch: int, r: int = 2, base: int = 0):
+    def relayout_two_rotations_deferred(self, ct, level: int, lo: Sequence[int], hi: Sequence[int], masks_ext, keys: Dict[int, np.ndarray]) -> np.ndarray:
+        """The same re-layout with the divisions by P deferred past the sums, as in the convolution's deferred schedule:
+            X_l  = Rot(ct, lo[l]) before its division (aligned_ext, one decomposition of ct for all l);
+            V_h  = ( sum_l M[h][l] (.) X_l ) / (P * q_level)           one merged division per h, level-1;
+            out  = ModDown( sum_h X'_h ),  X'_h = Rot(V_h, hi[h]) before its division          one ModDown.
+        masks_ext[h][l]: [level+1+k][N] on the extended basis, or None.  A first rotation costs an inner product only, so
+        plans with many first and few second rotations are cheap here.  Same slots as relayout_two_rotations up to
+        rounding noise, different residues.  Result [2][level][N]."""
+        ct = _u64(ct)
+        digits = self.modup(ct[1], level)
+        X = [self.aligned_ext(ct, level, r, keys.get(r), digits) for r in lo]
+        W = None
+        for h in range(len(hi)):
+            ls = [l for l in range(len(lo)) if masks_ext[h][l] is not None]
+            acc = self.mac_ext([masks_ext[h][l] for l in ls], [X[l] for l in ls], level)
+            V = np.stack([self.moddown_rescale(acc[0], level), self.moddown_rescale(acc[1], level)])
+            Xh = self.aligned_ext(V, level - 1, hi[h], keys.get(hi[h]), self.modup(V[1], level - 1))
+            W = Xh if W is None else self.add_ext(W, Xh, level - 1)
+        return np.stack([self.moddown(W[0], level - 1), self.moddown(W[1], level - 1)])
+
+    def downsample_plan(self, height: int, width: int, batch: int, r: int = 2, base: int = 0, rows_per_group: int = 1):
         """Slot compaction after a stride-r layer ("Optimized Inference Pipeline": H' = H/r, W' = W/r, sts' = sts/r^2;
         the paper leaves the compaction itself to its library).  Input layout: image j at slots [j*H*W, (j+1)*H*W)
         with the kept elements (y, x) = (r y', r x') at j*H*W + r*y'*W + r*x'.  Output layout: image j at slots
         [j*H'*W', (j+1)*H'*W'), everything else zero.  Two re-layouts of two rotations each:
-          A (inside every image):  element (y', x') moves left by x'*(r-1) [lo] + y'*(r*W - W') [hi];
+          A (inside every image):  element (y', x') moves left by x'*(r-1) + y'*(r*W - W'); with rows_per_group = G
+                                   (a divisor of H') the first rotation takes x'*(r-1) + (y' % G)*(r*W - W') and the
+                                   second (y' // G)*G*(r*W - W'): G*W' first and H'/G second rotations (G = 1: W' and H');
           B (whole images):        image j moves left by j*(H*W - H'*W') = (j % base)*d [lo] + (j // base)*base*d [hi].
         Returns [(lo, hi, slot_masks)] for A and B; slot_masks[h][l] is a 0/1 vector over the n slots (the positions of
         the selected elements after their first rotation) or None."""
         assert height % r == 0 and width % r == 0 and batch * height * width <= self.n
         hw, h2, w2 = height * width, height // r, width // r
+        G = rows_per_group
+        assert h2 % G == 0
         base = base or int(np.ceil(np.sqrt(batch)))
         j0 = np.arange(batch) * hw
-        lo_a = [x * (r - 1) for x in range(w2)]
-        hi_a = [y * (r * width - w2) for y in range(h2)]
+        dy = r * width - w2
+        lo_a = [yl * dy + x * (r - 1) for yl in range(G) for x in range(w2)]
+        hi_a = [yh * G * dy for yh in range(h2 // G)]
         masks_a = []
-        for y in range(h2):
+        for yh in range(h2 // G):
             row = []
-            for x in range(w2):
-                m = np.zeros(self.n)
-                m[j0 + r * y * width + r * x - lo_a[x]] = 1.0
-                row.append(m)
+            for yl in range(G):
+                for x in range(w2):
+                    m = np.zeros(self.n)
+                    m[j0 + r * (yh * G + yl) * width + r * x - lo_a[yl * w2 + x]] = 1.0
+                    row.append(m)
             masks_a.append(row)
         d = hw - h2 * w2
         lo_b = [l * d for l in range(min(base, batch))]
@@ -710,14 +745,19 @@ class Oracle:
             masks_b.append(row)
         return [(lo_a, hi_a, masks_a), (lo_b, hi_b, masks_b)]
 
-    def downsample_compact(self, ct, level: int, plan, keys: Dict[int, np.ndarray]) -> np.ndarray:
+    def downsample_compact(self, ct, level: int, plan, keys: Dict[int, np.ndarray], deferred: bool = False) -> np.ndarray:
         """Runs the two re-layouts of downsample_plan; every mask is encoded at the scale of the limb its product
         drops, so the ciphertext's scale is unchanged.  Input at `level`, output [2][level-1][N] at level-2."""
         ct = _u64(ct)
         for stage, (lo, hi, slot_masks) in enumerate(plan):
             lv = level - stage
-            masks = [[None if m is None else self.encode_ntt(m, float(self.moduli[lv]), lv) for m in row] for row in slot_masks]
-            ct = self.relayout_two_rotations(ct, lv, lo, hi, masks, keys)
+            if deferred:
+                ext = self.ext_moduli_idx(lv)
+                masks = [[None if m is None else self.lift_ntt(self.encode(m, float(self.moduli[lv])), ext) for m in row] for row in slot_masks]
+                ct = self.relayout_two_rotations_deferred(ct, lv, lo, hi, masks, keys)
+            else:
+                masks = [[None if m is None else self.encode_ntt(m, float(self.moduli[lv]), lv) for m in row] for row in slot_masks]
+                ct = self.relayout_two_rotations(ct, lv, lo, hi, masks, keys)
         return ct
 
     # ------------------------------------------- ciphertext product with the merged division

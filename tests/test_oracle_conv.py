@@ -297,13 +297,55 @@ def test_downsample_compaction_is_the_strided_selection(height, width, batch, r,
     assert np.abs(got[want.size:]).max() < 1e-5
 
 
-def test_downsample_plan_moves_every_kept_slot_exactly_once():
+@pytest.mark.parametrize("height,width,batch,r,base,group", [(4, 4, 8, 2, 3, 1), (4, 8, 5, 2, 5, 2), (8, 8, 2, 2, 1, 4)])
+def test_downsample_compaction_with_deferred_divisions(height, width, batch, r, base, group):
+    """The deferred schedule (sums on the extended basis, one merged division per second rotation, one ModDown) gives the
+    strided selection too, agrees with the plain schedule in the slots to rounding noise, and differs in the residues;
+    several rows per group (many first, few second rotations; group = H': no second rotation inside the images)."""
+    p = make_params(10, 5, 2, 3)
+    o = Oracle(p)
+    level = p.num_q - 1
+    s, s_ntt = o.gen_secret(14500)
+    X = np.random.default_rng(21).uniform(-1, 1, (batch, height, width))
+    z = np.random.default_rng(22).uniform(-1, 1, o.n)
+    z[:X.size] = X.reshape(-1)
+    scale = 2.0 ** 40
+    ct = o.encrypt(z, scale, level, s_ntt, 14501)
+    plan = o.downsample_plan(height, width, batch, r, base, rows_per_group=group)
+    keys = downsample_keys(o, s, s_ntt, plan, 14600)
+    out = o.downsample_compact(ct, level, plan, keys, deferred=True)
+    ref = o.downsample_compact(ct, level, plan, keys, deferred=False)
+    assert out.shape == ref.shape == (2, level - 1, o.N) and not np.array_equal(out, ref)
+    got = o.decrypt(out, level - 2, s_ntt, scale)
+    want = X[:, ::r, ::r].reshape(-1)
+    assert np.abs(got[:want.size] - want).max() < 1e-5 and np.abs(got[want.size:]).max() < 1e-5
+    assert np.abs(got - o.decrypt(ref, level - 2, s_ntt, scale)).max() < 1e-6
+
+
+def test_aligned_copy_divides_to_the_rotation():
+    """ModDown of the pre-division copy is the hoisted rotation, residue for residue (offset 0: the ciphertext itself)."""
+    p = make_params(10, 4, 2, 2)
+    o = Oracle(p)
+    level = p.num_q - 1
+    s, s_ntt = o.gen_secret(14700)
+    ct = o.encrypt(np.random.default_rng(23).uniform(-1, 1, o.n), 2.0 ** 40, level, s_ntt, 14701)
+    digits = o.modup(ct[1], level)
+    for off in (0, 7, -3):
+        key = o.gen_rotation_key(s, s_ntt, off, 14710 + off) if off else None
+        x = o.aligned_ext(ct, level, off, key, digits)
+        down = np.stack([o.moddown(x[0], level), o.moddown(x[1], level)])
+        assert np.array_equal(down, o.rotate(ct, level, off, key, True, digits))
+
+
+@pytest.mark.parametrize("group", [1, 2])
+def test_downsample_plan_moves_every_kept_slot_exactly_once(group):
     """The plan alone, on slot indices: following mask -> first rotation -> second rotation sends the slot of every kept
     element to its compact position, no two masks of a stage overlap after their rotations, and the slot accounting of the
     pipeline holds (sts' = sts / r^2)."""
     o = Oracle(make_params(10, 1, 0, 1))
     height, width, batch, r = 4, 8, 7, 2
-    (lo_a, hi_a, m_a), (lo_b, hi_b, m_b) = o.downsample_plan(height, width, batch, r, 3)
+    (lo_a, hi_a, m_a), (lo_b, hi_b, m_b) = o.downsample_plan(height, width, batch, r, 3, rows_per_group=group)
+    assert len(lo_a) == group * (width // r) and len(hi_a) == height // r // group
     pos = {}                                                       # slot -> (j, y', x') through the stages
     for j in range(batch):
         for y in range(height // r):
