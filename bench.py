@@ -330,40 +330,53 @@ def main():
     result["fc_layer_shape"] = {"d_in": fc_in, "d_out": fc_out, "batch": fc_batch, "level": fc_level, "base": fc_base,
                                 "key_switches": sum(k is not None for ks in fc_keys for k in ks) + (fc_out - 1) * 6}
     del fc_keys, fc_ws
-    # down-sampling compaction at the stage-2 -> stage-3 transition: 64 channel ciphertexts of 128 images of 16x16 -> 8x8
-    # (two re-layouts: inside the images 8 + 8 offsets, whole images base 12: 12 + 11), at the level the slice ends on
-    ds_level, ds_n = level - 5, 64
-    stages = [([x for x in range(8)], [y * 24 for y in range(8)]), ([l * 192 for l in range(12)], [h * 12 * 192 for h in range(11)])]
+    # down-sampling compaction at the stage-2 -> stage-3 transition: 64 channel ciphertexts of 128 images of 16x16 -> 8x8, at
+    # the level the slice ends on.  Two re-layouts (inside the images, then whole images), in two configurations:
+    #   direct    8 + 8 and 12 + 11 offsets, every rotation divided by P on its own (35 keys)
+    #   deferred  16 + 4 and 32 + 4 offsets, divisions after the sums: first rotations are inner products only (52 keys)
+    ds_level, ds_n, kp = level - 5, 64, params.num_p
     ds_in = [hx.empty(2, ds_level + 1, N).copy_(ins[i % len(ins)][:, :ds_level + 1]) for i in range(ds_n)]
-    ds_ws = hx.empty(max(hx.he_relayout_workspace_bytes(ctx, ds_level - k, ds_n, len(lo), len(hi)) for k, (lo, hi) in enumerate(stages)) // 8)
-    ds_args = []
-    for k, (lo, hi) in enumerate(stages):
-        lv = ds_level - k
-        mk = lambda offs, salt: [None if r % (N // 2) == 0 else
-                                 hx.ckks_key_load(ctx, base_keys[(salt + j) % len(base_keys)].tensor.clone(), hx.ckks_galois_element(ctx, r))
-                                 for j, r in enumerate(offs)]
-        n_pairs = len(lo) * len(hi) if k == 0 else 128          # stage B: one pair per image
-        ms = [[(masks[(h * len(lo) + l) % 9, :lv + 1].contiguous() if h * len(lo) + l < n_pairs else None) for l in range(len(lo))]
-              for h in range(len(hi))]
-        ds_args.append((lv, lo, mk(lo, 3 * k), hi, mk(hi, 3 * k + 5), ms, [hx.empty(2, lv, N) for _ in range(ds_n)]))
+    ds_plans = {
+        "direct": (hx.HE_RELAYOUT_DIRECT, [([x for x in range(8)], [y * 24 for y in range(8)], 64),
+                                            ([l * 192 for l in range(12)], [h * 12 * 192 for h in range(11)], 128)]),
+        "deferred": (hx.HE_RELAYOUT_DEFERRED, [([y * 24 + x for y in range(2) for x in range(8)], [h * 48 for h in range(4)], 64),
+                                                ([l * 192 for l in range(32)], [h * 32 * 192 for h in range(4)], 128)]),
+    }
+    for name, (sched, stages) in ds_plans.items():
+        ds_ws = hx.empty(max(hx.he_relayout_workspace_bytes(ctx, ds_level - k, ds_n, len(lo), len(hi), sched)
+                             for k, (lo, hi, _) in enumerate(stages)) // 8)
+        ds_args = []
+        for k, (lo, hi, n_pairs) in enumerate(stages):
+            lv = ds_level - k
+            mk = lambda offs, salt: [None if r % (N // 2) == 0 else
+                                     hx.ckks_key_load(ctx, base_keys[(salt + j) % len(base_keys)].tensor.clone(), hx.ckks_galois_element(ctx, r))
+                                     for j, r in enumerate(offs)]
+            if sched == hx.HE_RELAYOUT_DEFERRED:   # masks on the extended basis: the live q-limbs, then the special primes
+                pool = [torch.cat([masks[i, :lv + 1], masks[i, level + 1:level + 1 + kp]]).contiguous() for i in range(9)]
+            else:
+                pool = [masks[i, :lv + 1].contiguous() for i in range(9)]
+            ms = [[(pool[(h * len(lo) + l) % 9] if h * len(lo) + l < n_pairs else None) for l in range(len(lo))] for h in range(len(hi))]
+            ds_args.append((lv, lo, mk(lo, 3 * k), hi, mk(hi, 3 * k + 5), ms, [hx.empty(2, lv, N) for _ in range(ds_n)]))
 
-    def run_ds():
-        cur = ds_in
-        for lv, lo, lk, hi, hk, ms, outs in ds_args:
-            cur = hx.he_relayout_two_rotations(ctx, cur, lv, lo, lk, hi, hk, ms, outs=outs, ws=ds_ws)
-    run_ds()
-    torch.cuda.synchronize()
-    reps = 3
-    t0 = time.perf_counter()
-    for _ in range(reps):
+        def run_ds():
+            cur = ds_in
+            for lv, lo, lk, hi, hk, ms, outs in ds_args:
+                cur = hx.he_relayout_two_rotations(ctx, cur, lv, lo, lk, hi, hk, ms, schedule=sched, outs=outs, ws=ds_ws)
         run_ds()
-    torch.cuda.synchronize()
-    ds_dt = (time.perf_counter() - t0) / reps
-    result["downsample_ms"] = ds_dt * 1e3
-    result["downsample_ms_per_image"] = ds_dt * 1e3 / 128
-    result["downsample_shape"] = {"channels": ds_n, "from": "16x16", "to": "8x8", "batch": 128, "level": ds_level,
-                                  "key_switches": ds_n * sum(sum(1 for r in lo + hi if r % (N // 2)) for lo, hi in stages)}
-    del ds_args, ds_ws, ds_in
+        torch.cuda.synchronize()
+        reps = 3
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            run_ds()
+        torch.cuda.synchronize()
+        ds_dt = (time.perf_counter() - t0) / reps
+        result["downsample_%s" % name] = {
+            "ms": ds_dt * 1e3, "ms_per_image": ds_dt * 1e3 / 128, "offsets": [[len(lo), len(hi)] for lo, hi, _ in stages],
+            "keys": sum(1 for lo, hi, _ in stages for r in lo + hi if r % (N // 2)),
+            "inner_products": ds_n * sum(1 for lo, hi, _ in stages for r in lo + hi if r % (N // 2))}
+        del ds_args, ds_ws
+    result["downsample_shape"] = {"channels": ds_n, "from": "16x16", "to": "8x8", "batch": 128, "level": ds_level}
+    del ds_in
     # key staging: the block group's 9 keys (8 rotations + relinearisation) as b halves in pinned host memory (48 MiB
     # each) + seeds, copied and expanded on a side stream, alone and while the block slice runs on the main stream
     n_stage = 9

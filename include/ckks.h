@@ -220,13 +220,20 @@ int he_accumulator_merge(const ckks_ctx* ctx, const uint64_t* const* h_d_cts, ui
  * over whole images (lo = (j mod base) d, hi = (j div base) base d, d = HW - H'W').
  * h_d_cts[b] uint64[2][level+1][N], level >= 1; h_lo / h_hi: host arrays of slot offsets (0 = no rotation, key
  * ignored); lo_keys[l] / hi_keys[h] made for those offsets; h_d_masks: host array of n_hi*n_lo device pointers,
- * entry h*n_lo + l is uint64[level+1][N] (NTT form) or NULL when no element takes that pair (every h needs one
- * mask at least); h_d_outs[b] uint64[2][level][N], one level lower.  Outputs must not overlap inputs. */
-size_t he_relayout_workspace_bytes(const ckks_ctx* ctx, uint32_t level, uint32_t n_ct, uint32_t n_lo, uint32_t n_hi);
+ * entry h*n_lo + l is a plaintext in NTT form or NULL when no element takes that pair (every h needs one mask at
+ * least); h_d_outs[b] uint64[2][level][N], one level lower.  Outputs must not overlap inputs.
+ * schedule HE_RELAYOUT_DIRECT: every rotation is completed (divided by P) on its own; masks uint64[level+1][N].
+ * schedule HE_RELAYOUT_DEFERRED: the divisions by P come after the sums, as in the convolution's deferred schedules:
+ * the first rotations stay on the extended basis Q_level P, each inner sum takes one division by P*q_level, the second
+ * rotations are summed on the extended basis of level-1 and divided by P once; masks uint64[level+1+num_p][N] on the
+ * extended basis.  A first rotation then costs an inner product only.  Same slots, different residues. */
+enum he_relayout_schedule { HE_RELAYOUT_DIRECT = 0, HE_RELAYOUT_DEFERRED = 1 };
+size_t he_relayout_workspace_bytes(const ckks_ctx* ctx, uint32_t level, uint32_t n_ct, uint32_t n_lo, uint32_t n_hi,
+                                   uint32_t schedule);
 int he_relayout_two_rotations(const ckks_ctx* ctx, const uint64_t* const* h_d_cts, uint32_t n_ct, uint32_t level,
                               const int32_t* h_lo, uint32_t n_lo, const ckks_key* const* lo_keys, const int32_t* h_hi,
                               uint32_t n_hi, const ckks_key* const* hi_keys, const uint64_t* const* h_d_masks,
-                              uint64_t* const* h_d_outs, void* d_ws, size_t ws_bytes, void* stream);
+                              uint32_t schedule, uint64_t* const* h_d_outs, void* d_ws, size_t ws_bytes, void* stream);
 
 /* Batched fully connected layer ("Fully Connected Layer": FC evaluation and output reconstruction).  The input
  * ciphertext holds x^(j) (d_in values, d_in a power of two) in slots [j*d_in, (j+1)*d_in) for j < batch

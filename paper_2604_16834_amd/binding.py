@@ -36,6 +36,8 @@ HE_CONV_ALIGN_DIRECT = 0
 HE_CONV_ALIGN_FOUR_KEYS = 1
 HE_CONV_DEFERRED_MODDOWN = 2
 HE_CONV_DEFERRED_MERGED = 3
+HE_RELAYOUT_DIRECT = 0
+HE_RELAYOUT_DEFERRED = 1
 
 EXPORTS = (
     "ckks_ctx_create", "ckks_ctx_destroy", "ckks_last_error_string", "ckks_workspace_bytes",
@@ -105,10 +107,10 @@ def _bind(path: str):
     lib.he_fc_workspace_bytes.restype = sz
     lib.he_fc_batched.argtypes = [vp, C.POINTER(_FcDesc), vp, vp, C.POINTER(vp), C.POINTER(vp), vp, vp, C.POINTER(vp), C.POINTER(vp),
                                   vp, vp, vp, sz, vp]
-    lib.he_relayout_workspace_bytes.argtypes = [vp, u32, u32, u32, u32]
+    lib.he_relayout_workspace_bytes.argtypes = [vp, u32, u32, u32, u32, u32]
     lib.he_relayout_workspace_bytes.restype = sz
     lib.he_relayout_two_rotations.argtypes = [vp, C.POINTER(vp), u32, u32, C.POINTER(C.c_int32), u32, C.POINTER(vp), C.POINTER(C.c_int32),
-                                              u32, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), vp, sz, vp]
+                                              u32, C.POINTER(vp), C.POINTER(vp), u32, C.POINTER(vp), vp, sz, vp]
     lib.ckks_key_expand_a.argtypes = [vp, C.c_uint64, vp, vp]
     lib.ckks_keyset_stage.argtypes = [vp, C.POINTER(vp), C.POINTER(C.c_uint64), C.POINTER(vp), u32, vp]
     lib.ckks_prof_kernel_count.restype = u32
@@ -437,15 +439,16 @@ def ckks_keyset_stage(ctx: Context, host_b: Sequence[torch.Tensor], a_seeds: Seq
     ctx._check(_lib.ckks_keyset_stage(ctx.handle, hb_arr, seeds, _ptr_array([_ptr(k) for k in keys]), n, _stream(stream)))
 
 
-def he_relayout_workspace_bytes(ctx: Context, level: int, n_ct: int, n_lo: int, n_hi: int) -> int:
-    return int(_lib.he_relayout_workspace_bytes(ctx.handle, level, n_ct, n_lo, n_hi))
+def he_relayout_workspace_bytes(ctx: Context, level: int, n_ct: int, n_lo: int, n_hi: int, schedule: int = HE_RELAYOUT_DIRECT) -> int:
+    return int(_lib.he_relayout_workspace_bytes(ctx.handle, level, n_ct, n_lo, n_hi, schedule))
 
 
 def he_relayout_two_rotations(ctx: Context, cts: Sequence[torch.Tensor], level: int, lo: Sequence[int], lo_keys: Sequence[Optional[Key]],
                               hi: Sequence[int], hi_keys: Sequence[Optional[Key]], masks: Sequence[Sequence[Optional[torch.Tensor]]],
-                              outs: Optional[Sequence[torch.Tensor]] = None, ws: Optional[torch.Tensor] = None,
-                              stream=None) -> List[torch.Tensor]:
-    """out_b = sum_h Rot(Rescale(sum_l masks[h][l] (.) Rot(cts[b], lo[l])), hi[h]); masks[h][l] is [level+1][N] or None.
+                              schedule: int = HE_RELAYOUT_DIRECT, outs: Optional[Sequence[torch.Tensor]] = None,
+                              ws: Optional[torch.Tensor] = None, stream=None) -> List[torch.Tensor]:
+    """out_b = sum_h Rot(Rescale(sum_l masks[h][l] (.) Rot(cts[b], lo[l])), hi[h]); masks[h][l] is [level+1][N]
+    (HE_RELAYOUT_DIRECT) or [level+1+num_p][N] on the extended basis (HE_RELAYOUT_DEFERRED), or None.
     cts[b] [2][level+1][N]; returns [2][level][N] per ciphertext."""
     n_ct, n_lo, n_hi = len(cts), len(lo), len(hi)
     if len(lo_keys) != n_lo or len(hi_keys) != n_hi or len(masks) != n_hi or any(len(row) != n_lo for row in masks):
@@ -453,20 +456,21 @@ def he_relayout_two_rotations(ctx: Context, cts: Sequence[torch.Tensor], level: 
     for t in cts:
         if t.numel() != 2 * (level + 1) * ctx.N:
             raise ValueError("each ciphertext must be [2][level+1][N]")
+    mask_limbs = level + 1 + (ctx.num_p if schedule == HE_RELAYOUT_DEFERRED else 0)
     for row in masks:
         for m in row:
-            if m is not None and m.numel() != (level + 1) * ctx.N:
-                raise ValueError("each mask must be [level+1][N]")
+            if m is not None and m.numel() != mask_limbs * ctx.N:
+                raise ValueError(f"each mask must be [{mask_limbs}][N]")
     if outs is None:
         outs = [empty(2, max(level, 1), ctx.N) for _ in range(n_ct)]
     for t in outs:
         if t.numel() != 2 * level * ctx.N:
             raise ValueError("each output must be [2][level][N]")
-    ws = _ws(ctx, ws, he_relayout_workspace_bytes(ctx, level, n_ct, n_lo, n_hi))
+    ws = _ws(ctx, ws, he_relayout_workspace_bytes(ctx, level, n_ct, n_lo, n_hi, schedule))
     arr = lambda ks: _ptr_array([k.handle.value if k is not None else None for k in ks])
     i32 = lambda v: (C.c_int32 * len(v))(*[int(x) for x in v])
     ctx._check(_lib.he_relayout_two_rotations(ctx.handle, _ptr_array([_ptr(t) for t in cts]), n_ct, level, i32(lo), n_lo, arr(lo_keys),
-                                              i32(hi), n_hi, arr(hi_keys), _ptr_array([_ptr(m) for row in masks for m in row]),
+                                              i32(hi), n_hi, arr(hi_keys), _ptr_array([_ptr(m) for row in masks for m in row]), schedule,
                                               _ptr_array([_ptr(t) for t in outs]), _ptr(ws), ws.numel() * ws.element_size(),
                                               _stream(stream)))
     return list(outs)

@@ -416,18 +416,7 @@ int run_relayout(const ckks_ctx* c, u32 level, u32 n_ct, const u64* const* cts, 
             if (nk && (rc = run_moddown(c, level, ws, nk, items, st))) return rc;
         }
         // masked sums, one per (ciphertext, h), and their rescale
-        std::vector<const u64*> pts, rts;
-        for (u32 b = 0; b < n; b++)
-            for (u32 h = 0; h < n_hi; h++) {
-                pts.clear();
-                rts.clear();
-                for (u32 l = 0; l < n_lo; l++)
-                    if (masks[(size_t)h * n_lo + l]) {
-                        pts.push_back(masks[(size_t)h * n_lo + l]);
-                        rts.push_back(r_at(b, l));
-                    }
-                HIP_TRY(launch_ptct_mac(c, level, pts.data(), rts.data(), (u32)pts.size(), Vacc + ((size_t)b * n_hi + h) * ctl, 0, st));
-            }
+        HIP_TRY(launch_relayout_mac(c, level, false, R, masks, Vacc, n, n_lo, n_hi, st));
         const u32 n_v = n * n_hi;
         for (u32 i0 = 0; i0 < n_v; i0 += CT_BATCH) {
             const u32 m = n_v - i0 < CT_BATCH ? n_v - i0 : CT_BATCH;
@@ -470,6 +459,120 @@ int run_relayout(const ckks_ctx* c, u32 level, u32 n_ct, const u64* const* cts, 
                 HIP_TRY(launch_ct_sum(c, l1, ptr_list(terms, nt), nt, out, st));
             }
         }
+    }
+    return CKKS_OK;
+}
+
+// The same re-layout with the divisions by P deferred past the sums (masks on the extended basis, [level+1+k][N]):
+//   X_l = (P sigma(c0) + v0, v1) for the first rotations (inner products only), V_h = (sum_l M[h][l] (.) X_l) / (P q_level),
+//   out = ModDown( sum_h X'_h ) with X'_h the pre-division copy of Rot(V_h, hi_h).
+size_t ws_relayout_deferred(const ckks_ctx* c, u32 level, u32 n_ct, u32 n_lo, u32 n_hi) {
+    const size_t N = c->N, xel = 2 * (size_t)c->ext_limbs(level) * N, xel1 = 2 * (size_t)c->ext_limbs(level - 1) * N, ctl1 = 2 * (size_t)level * N;
+    const size_t nb = n_ct < CT_BATCH ? n_ct : CT_BATCH;
+    return blk(nb * n_lo * xel) + blk(nb * n_hi * xel) + blk(nb * n_hi * ctl1) + blk(nb * n_hi * xel1) + blk(nb * xel1) +
+           ws_ks(c, level, CT_BATCH, CT_BATCH);
+}
+
+int run_relayout_deferred(const ckks_ctx* c, u32 level, u32 n_ct, const u64* const* cts, u32 n_lo, const ckks_key* const* lo_keys,
+                          const u32* g_lo, u32 n_hi, const ckks_key* const* hi_keys, const u32* g_hi, const u64* const* masks,
+                          u64* const* outs, Arena ar, hipStream_t st) {
+    const u32 l1 = level - 1, nb_max = n_ct < CT_BATCH ? n_ct : CT_BATCH;
+    const size_t N = c->N, xel = 2 * (size_t)c->ext_limbs(level) * N, xel1 = 2 * (size_t)c->ext_limbs(l1) * N, ctl1 = 2 * (size_t)level * N;
+    u64* X = ar.take((size_t)nb_max * n_lo * xel);     // first rotations before their division
+    u64* Vacc = ar.take((size_t)nb_max * n_hi * xel);  // masked sums on the extended basis
+    u64* V = ar.take((size_t)nb_max * n_hi * ctl1);    // divided by P q_level: level-1
+    u64* Xh = ar.take((size_t)nb_max * n_hi * xel1);   // second rotations before their division
+    u64* W = ar.take((size_t)nb_max * xel1);           // their sums
+    KsWs ws;
+    const size_t ks_bytes = ws_ks(c, level, CT_BATCH, CT_BATCH);
+    u64* ks_region = ar.take(ks_bytes / sizeof(u64));
+    if (!ar.ok()) return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for the re-layout");
+    auto ks_at = [&](u32 lv) {
+        Arena sub(ks_region, ks_bytes);
+        return carve_ks(c, lv, CT_BATCH, CT_BATCH, sub, ws);
+    };
+    int rc;
+    for (u32 c0 = 0; c0 < n_ct; c0 += CT_BATCH) {
+        const u32 n = n_ct - c0 < CT_BATCH ? n_ct - c0 : CT_BATCH;
+        ks_at(level);
+        const u64 *in[CT_BATCH], *c1s[CT_BATCH];
+        for (u32 b = 0; b < n; b++) {
+            in[b] = cts[c0 + b];
+            c1s[b] = in[b] + (size_t)(level + 1) * N;
+        }
+        if ((rc = run_modup(c, level, c1s, n, ws, st))) return rc;
+        for (u32 l = 0; l < n_lo; l++) {
+            u64* xo[CT_BATCH];
+            for (u32 b = 0; b < n; b++) xo[b] = X + ((size_t)b * n_lo + l) * xel;
+            if (g_lo[l] == 1) {
+                for (u32 b = 0; b < n; b++) HIP_TRY(launch_scale_p_ext(c, level, in[b], xo[b], st));
+            } else {
+                HIP_TRY(launch_key_inner_ext(c, level, ws.digits, ws.dig_b, lo_keys[l]->d_key, g_lo[l], in, nullptr, nullptr, xo, n, st));
+            }
+        }
+        HIP_TRY(launch_relayout_mac(c, level, true, X, masks, Vacc, n, n_lo, n_hi, st));
+        const u32 n_v = n * n_hi;
+        for (u32 i0 = 0; i0 < n_v; i0 += CT_BATCH) {  // one division by P q_level per sum
+            const u32 m = n_v - i0 < CT_BATCH ? n_v - i0 : CT_BATCH;
+            KsWs wd = ws;
+            wd.v = Vacc + (size_t)i0 * xel;
+            wd.v_b = xel;
+            FinalItem items[CT_BATCH];
+            for (u32 i = 0; i < m; i++) items[i] = FinalItem{nullptr, nullptr, nullptr, V + (size_t)(i0 + i) * ctl1, 1, 0};
+            if ((rc = run_moddown(c, level, wd, m, items, st, true))) return rc;
+        }
+        // second rotations on the extended basis of level-1, ordered by h so that the ciphertexts of a batch share each key
+        ks_at(l1);
+        const u64 *src[CT_BATCH], *sc1[CT_BATCH];
+        const ckks_key* ks[CT_BATCH];
+        u32 gs[CT_BATCH], nk = 0;
+        u64* dst[CT_BATCH];
+        auto flush = [&]() -> int {
+            int r = run_modup(c, l1, sc1, nk, ws, st);
+            if (r) return r;
+            for (u32 b0 = 0; b0 < nk;) {
+                u32 b1 = b0 + 1;
+                while (b1 < nk && ks[b1] == ks[b0]) b1++;
+                HIP_TRY(launch_key_inner_ext(c, l1, ws.digits + b0 * ws.dig_b, ws.dig_b, ks[b0]->d_key, gs[b0], src + b0, nullptr, nullptr,
+                                             dst + b0, b1 - b0, st));
+                b0 = b1;
+            }
+            nk = 0;
+            return CKKS_OK;
+        };
+        for (u32 h = 0; h < n_hi; h++)
+            for (u32 b = 0; b < n; b++) {
+                const u64* v = V + ((size_t)b * n_hi + h) * ctl1;
+                u64* xh = Xh + ((size_t)b * n_hi + h) * xel1;
+                if (g_hi[h] == 1) {
+                    HIP_TRY(launch_scale_p_ext(c, l1, v, xh, st));
+                    continue;
+                }
+                src[nk] = v;
+                sc1[nk] = v + (size_t)level * N;
+                dst[nk] = xh;
+                ks[nk] = hi_keys[h];
+                gs[nk++] = g_hi[h];
+                if (nk == CT_BATCH && (rc = flush())) return rc;
+            }
+        if (nk && (rc = flush())) return rc;
+        // sums on the extended basis, then one ModDown per ciphertext
+        for (u32 b = 0; b < n; b++) {
+            u64* w = W + (size_t)b * xel1;
+            for (u32 h = 0; h < n_hi;) {
+                const u64* terms[KS_MAX_BATCH];
+                u32 nt = 0;
+                if (h) terms[nt++] = w;
+                for (; h < n_hi && nt < KS_MAX_BATCH; h++) terms[nt++] = Xh + ((size_t)b * n_hi + h) * xel1;
+                HIP_TRY(launch_ct_sum(c, l1, ptr_list(terms, nt), nt, w, st, true));
+            }
+        }
+        KsWs wd = ws;
+        wd.v = W;
+        wd.v_b = xel1;
+        FinalItem items[CT_BATCH];
+        for (u32 b = 0; b < n; b++) items[b] = FinalItem{nullptr, nullptr, nullptr, outs[c0 + b], 1, 0};
+        if ((rc = run_moddown(c, l1, wd, n, items, st))) return rc;
     }
     return CKKS_OK;
 }
@@ -879,18 +982,19 @@ int he_accumulator_merge(const ckks_ctx* c, const uint64_t* const* h_d_cts, uint
 }
 
 // ---- slot re-layout with two rotations per element (down-sampling compaction, FC output reconstruction) ----
-size_t he_relayout_workspace_bytes(const ckks_ctx* c, uint32_t level, uint32_t n_ct, uint32_t n_lo, uint32_t n_hi) {
-    if (!c || !c->dnum || !level_ok(c, level) || level < 1 || n_ct == 0 || n_lo == 0 || n_hi == 0) return 0;
-    return ws_relayout(c, level, n_ct, n_lo, n_hi);
+size_t he_relayout_workspace_bytes(const ckks_ctx* c, uint32_t level, uint32_t n_ct, uint32_t n_lo, uint32_t n_hi, uint32_t schedule) {
+    if (!c || !c->dnum || !level_ok(c, level) || level < 1 || n_ct == 0 || n_lo == 0 || n_hi == 0 || schedule > HE_RELAYOUT_DEFERRED) return 0;
+    return schedule == HE_RELAYOUT_DEFERRED ? ws_relayout_deferred(c, level, n_ct, n_lo, n_hi) : ws_relayout(c, level, n_ct, n_lo, n_hi);
 }
 
 int he_relayout_two_rotations(const ckks_ctx* c, const uint64_t* const* h_d_cts, uint32_t n_ct, uint32_t level, const int32_t* h_lo,
                               uint32_t n_lo, const ckks_key* const* lo_keys, const int32_t* h_hi, uint32_t n_hi,
-                              const ckks_key* const* hi_keys, const uint64_t* const* h_d_masks, uint64_t* const* h_d_outs, void* d_ws,
-                              size_t ws_bytes, void* stream) {
+                              const ckks_key* const* hi_keys, const uint64_t* const* h_d_masks, uint32_t schedule,
+                              uint64_t* const* h_d_outs, void* d_ws, size_t ws_bytes, void* stream) {
     if (!c) return CKKS_ERR_INVALID_ARG;
     if (!h_d_cts || !h_lo || !h_hi || !h_d_masks || !h_d_outs || n_ct == 0 || n_lo == 0 || n_hi == 0)
         return set_err(c, CKKS_ERR_INVALID_ARG, "null pointer or an empty list");
+    if (schedule > HE_RELAYOUT_DEFERRED) return set_err(c, CKKS_ERR_INVALID_ARG, "unknown schedule");
     if (!c->dnum) return set_err(c, CKKS_ERR_UNSUPPORTED_PARAMS, "context has no key-switching digits");
     if (!level_ok(c, level) || level < 1) return set_err(c, CKKS_ERR_LEVEL_MISMATCH, "the re-layout needs 1 <= level < num_q");
     if ((u64)n_lo * n_hi > (u64)c->N) return set_err(c, CKKS_ERR_INVALID_ARG, "more (lo, hi) pairs than coefficients");
@@ -910,8 +1014,9 @@ int he_relayout_two_rotations(const ckks_ctx* c, const uint64_t* const* h_d_cts,
         for (u32 l = 0; l < n_lo; l++) any = any || h_d_masks[(size_t)h * n_lo + l];
         if (!any) return set_err(c, CKKS_ERR_INVALID_ARG, "a second rotation has no mask at all");
     }
-    return run_relayout(c, level, n_ct, (const u64* const*)h_d_cts, n_lo, lo_keys, g_lo.data(), n_hi, hi_keys, g_hi.data(),
-                        (const u64* const*)h_d_masks, (u64* const*)h_d_outs, Arena(d_ws, ws_bytes), (hipStream_t)stream);
+    return (schedule == HE_RELAYOUT_DEFERRED ? run_relayout_deferred : run_relayout)(
+        c, level, n_ct, (const u64* const*)h_d_cts, n_lo, lo_keys, g_lo.data(), n_hi, hi_keys, g_hi.data(), (const u64* const*)h_d_masks,
+        (u64* const*)h_d_outs, Arena(d_ws, ws_bytes), (hipStream_t)stream);
 }
 
 // ---- batched fully connected layer ------------------------------------------------------------------

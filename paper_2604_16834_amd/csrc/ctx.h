@@ -186,7 +186,10 @@ hipError_t launch_moddown_final(const ckks_ctx* c, u32 level, bool merged, const
 hipError_t launch_automorph(const ckks_ctx* c, u32 n_polys, const u64* in, u32 g, u64* out, hipStream_t st);
 hipError_t launch_copy(const u64* in, u64* out, size_t n, hipStream_t st);
 hipError_t launch_ptct_mac(const ckks_ctx* c, u32 level, const u64* const* pts, const u64* const* cts, u32 n_terms, u64* acc,
-                           int accumulate, hipStream_t st);
+                           int accumulate, hipStream_t st, bool extended = false);
+hipError_t launch_relayout_mac(const ckks_ctx* c, u32 level, bool extended, const u64* xs, const u64* const* masks, u64* acc, u32 n,
+                               u32 n_lo, u32 n_hi, hipStream_t st);
+hipError_t launch_scale_p_ext(const ckks_ctx* c, u32 level, const u64* ct, u64* out, hipStream_t st);
 hipError_t launch_rescale_conv(const ckks_ctx* c, u32 level, const u64* r, u64* w, u32 batch, hipStream_t st);
 hipError_t launch_rescale_final(const ckks_ctx* c, u32 level, const PtrList8& ct, size_t ct_cstride, const u64* w, const OutList8& out,
                                 u32 n, hipStream_t st);
@@ -195,7 +198,7 @@ hipError_t launch_tensor(const ckks_ctx* c, u32 level, const PtrList8& a, size_t
 hipError_t launch_mask_mul(const ckks_ctx* c, u32 level, const u64* mask, const u64* ct, u64* out, hipStream_t st);
 hipError_t launch_key_expand_a(const ckks_ctx* c, u64 seed, u64* key, hipStream_t st);
 hipError_t launch_add_plain(const ckks_ctx* c, u32 level, const u64* pt, u64* ct, hipStream_t st);
-hipError_t launch_ct_sum(const ckks_ctx* c, u32 level, const PtrList8& items, u32 n, u64* out, hipStream_t st);
+hipError_t launch_ct_sum(const ckks_ctx* c, u32 level, const PtrList8& items, u32 n, u64* out, hipStream_t st, bool extended = false);
 hipError_t launch_centre_ext(const ckks_ctx* c, u32 level, const u64* mask, const u64* ct, u64* xs, XLayout xl, u32 k, hipStream_t st);
 size_t weighted_sum_scratch_elems(const ckks_ctx* c, u32 n_limbs, u32 n_terms, u32 c_out);
 hipError_t launch_weighted_sum(const ckks_ctx* c, u32 level, bool extended, const u64* xs, XLayout xl, u32 n_terms, const u64* w_res,

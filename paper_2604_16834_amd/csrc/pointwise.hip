@@ -50,13 +50,14 @@ struct MacTerms {
     u32 n;
 };
 
+// limbs = level+1 (ciphertext limbs) or level+1+k (extended basis Q_level P: positions above `level` are the special primes)
 __global__ __launch_bounds__(PW_THREADS) void ptct_mac_kernel(MacTerms T, u64* __restrict__ acc, const ModConst* __restrict__ mc,
-                                                              u32 N, u32 level, int accumulate) {
+                                                              u32 N, u32 level, u32 limbs, u32 num_q, int accumulate) {
     const u32 x = blockIdx.x * PW_THREADS + threadIdx.x;
     if (x >= N) return;
     const u32 i = blockIdx.y, comp = blockIdx.z;
-    const ModConst m = mc[i];
-    const size_t po = (size_t)i * N + x, co = ((size_t)comp * (level + 1) + i) * N + x;
+    const ModConst m = mc[i <= level ? i : num_q + (i - level - 1)];
+    const size_t po = (size_t)i * N + x, co = ((size_t)comp * limbs + i) * N + x;
     U128 s = {0, 0};
     if (accumulate) s.lo = acc[co];
     for (u32 k = 0; k < T.n; k++) acc_wide(s, T.pt[k][po], T.ct[k][co]);
@@ -64,8 +65,9 @@ __global__ __launch_bounds__(PW_THREADS) void ptct_mac_kernel(MacTerms T, u64* _
 }
 
 hipError_t launch_ptct_mac(const ckks_ctx* c, u32 level, const u64* const* pts, const u64* const* cts, u32 n_terms, u64* acc,
-                           int accumulate, hipStream_t st) {
-    dim3 grid((c->N + PW_THREADS - 1) / PW_THREADS, level + 1, 2);
+                           int accumulate, hipStream_t st, bool extended) {
+    const u32 limbs = extended ? c->ext_limbs(level) : level + 1;
+    dim3 grid((c->N + PW_THREADS - 1) / PW_THREADS, limbs, 2);
     for (u32 k0 = 0; k0 < n_terms; k0 += MAC_TERMS_PER_LAUNCH) {
         MacTerms T;
         T.n = n_terms - k0 < MAC_TERMS_PER_LAUNCH ? n_terms - k0 : MAC_TERMS_PER_LAUNCH;
@@ -73,7 +75,96 @@ hipError_t launch_ptct_mac(const ckks_ctx* c, u32 level, const u64* const* pts, 
             T.pt[k] = k < T.n ? pts[k0 + k] : nullptr;
             T.ct[k] = k < T.n ? cts[k0 + k] : nullptr;
         }
-        { ProfScope ps__(c, K_PTCT_MAC, st, 8.0 * c->N * (level + 1.0) * (3.0 * T.n + 2.0 + ((accumulate || k0 > 0) ? 2.0 : 0.0)), 2.0 * c->N * (level + 1.0) * T.n); hipLaunchKernelGGL(ptct_mac_kernel, grid, dim3(PW_THREADS), 0, st, T, acc, c->d_mc, c->N, level, accumulate || k0 > 0); }
+        ProfScope ps__(c, K_PTCT_MAC, st, 8.0 * c->N * limbs * (3.0 * T.n + 2.0 + ((accumulate || k0 > 0) ? 2.0 : 0.0)), 2.0 * c->N * limbs * T.n);
+        hipLaunchKernelGGL(ptct_mac_kernel, grid, dim3(PW_THREADS), 0, st, T, acc, c->d_mc, c->N, level, limbs, c->num_q, accumulate || k0 > 0);
+    }
+    return hipGetLastError();
+}
+
+// ---- the masked sums of a re-layout, all of them in one pass over the rotated copies --------------------------
+//   acc[b][h] = sum_l mask[h][l] (.) x[b][l]      b < n ciphertexts, h < n_hi, l < n_lo
+// x[b][l] = xs + (b*n_lo + l)*stride, acc[b][h] = acc + (b*n_hi + h)*stride, each [2][limbs][N].  A thread owns one
+// (coefficient, limb) of RL_CB ciphertexts and keeps the sums of up to RL_NH values of h, so every rotated copy is
+// read once per group of RL_NH sums (a launch per (h, l) pair list read it once per sum) and every mask word once per
+// RL_CB ciphertexts.  Absent pairs are null pointers.
+#define RL_NH 4
+#define RL_CB 4
+#define RL_NL 32
+struct RelayoutMasks {
+    const u64* m[RL_NH][RL_NL];
+};
+
+__global__ __launch_bounds__(PW_THREADS) void relayout_mac_kernel(const u64* __restrict__ xs, RelayoutMasks M, u64* __restrict__ acc,
+                                                                  const ModConst* __restrict__ mc, u32 N, u32 level, u32 limbs, u32 num_q,
+                                                                  size_t stride, u32 n, u32 n_lo, u32 n_hi, u32 l0, u32 nl, u32 h0,
+                                                                  u32 nh, int accumulate) {
+    const u32 x = blockIdx.x * PW_THREADS + threadIdx.x;
+    if (x >= N) return;
+    const u32 i = blockIdx.y, b0 = blockIdx.z * RL_CB;
+    const ModConst m = mc[i <= level ? i : num_q + (i - level - 1)];
+    const size_t po = (size_t)i * N + x;
+    U128 s[RL_NH][RL_CB][2];
+#pragma unroll
+    for (u32 h = 0; h < RL_NH; h++)
+#pragma unroll
+        for (u32 b = 0; b < RL_CB; b++)
+#pragma unroll
+            for (u32 comp = 0; comp < 2; comp++) {
+                s[h][b][comp] = {0, 0};
+                if (accumulate && h < nh && b0 + b < n)
+                    s[h][b][comp].lo = acc[((size_t)(b0 + b) * n_hi + h0 + h) * stride + ((size_t)comp * limbs + i) * N + x];
+            }
+    for (u32 l = 0; l < nl; l++) {
+        u64 xv[RL_CB][2];
+#pragma unroll
+        for (u32 b = 0; b < RL_CB; b++)
+#pragma unroll
+            for (u32 comp = 0; comp < 2; comp++)
+                xv[b][comp] = b0 + b < n ? xs[((size_t)(b0 + b) * n_lo + l0 + l) * stride + ((size_t)comp * limbs + i) * N + x] : 0;
+#pragma unroll
+        for (u32 h = 0; h < RL_NH; h++) {
+            const u64* mp = M.m[h][l];
+            if (h >= nh || !mp) continue;  // uniform over the workgroup
+            const u64 mv = mp[po];
+#pragma unroll
+            for (u32 b = 0; b < RL_CB; b++)
+#pragma unroll
+                for (u32 comp = 0; comp < 2; comp++) acc_wide(s[h][b][comp], mv, xv[b][comp]);
+        }
+    }
+#pragma unroll
+    for (u32 h = 0; h < RL_NH; h++)
+#pragma unroll
+        for (u32 b = 0; b < RL_CB; b++)
+#pragma unroll
+            for (u32 comp = 0; comp < 2; comp++)
+                if (h < nh && b0 + b < n)
+                    acc[((size_t)(b0 + b) * n_hi + h0 + h) * stride + ((size_t)comp * limbs + i) * N + x] = barrett_reduce(s[h][b][comp], m);
+}
+
+// masks: host array of n_hi*n_lo device pointers ([limbs][N] each, or null)
+hipError_t launch_relayout_mac(const ckks_ctx* c, u32 level, bool extended, const u64* xs, const u64* const* masks, u64* acc, u32 n,
+                               u32 n_lo, u32 n_hi, hipStream_t st) {
+    const u32 limbs = extended ? c->ext_limbs(level) : level + 1;
+    const size_t stride = 2 * (size_t)limbs * c->N;
+    const u32 nl_max = c->lazy_terms < RL_NL ? (c->lazy_terms ? c->lazy_terms : 1) : RL_NL;  // products summed before a reduction
+    dim3 grid((c->N + PW_THREADS - 1) / PW_THREADS, limbs, (n + RL_CB - 1) / RL_CB);
+    for (u32 h0 = 0; h0 < n_hi; h0 += RL_NH) {
+        const u32 nh = n_hi - h0 < RL_NH ? n_hi - h0 : RL_NH;
+        for (u32 l0 = 0; l0 < n_lo; l0 += nl_max) {
+            const u32 nl = n_lo - l0 < nl_max ? n_lo - l0 : nl_max;
+            RelayoutMasks M;
+            double n_masks = 0.0;
+            for (u32 h = 0; h < RL_NH; h++)
+                for (u32 l = 0; l < RL_NL; l++) {
+                    M.m[h][l] = (h < nh && l < nl) ? masks[(size_t)(h0 + h) * n_lo + l0 + l] : nullptr;
+                    n_masks += M.m[h][l] ? 1.0 : 0.0;
+                }
+            ProfScope ps__(c, K_PTCT_MAC, st, 8.0 * c->N * limbs * (2.0 * n * nl + n_masks * ((n + RL_CB - 1) / RL_CB) + 2.0 * n * nh * (l0 ? 2.0 : 1.0)),
+                           2.0 * c->N * limbs * n * n_masks);
+            hipLaunchKernelGGL(relayout_mac_kernel, grid, dim3(PW_THREADS), 0, st, xs, M, acc, c->d_mc, c->N, level, limbs, c->num_q, stride, n,
+                               n_lo, n_hi, l0, nl, h0, nh, l0 > 0 ? 1 : 0);
+        }
     }
     return hipGetLastError();
 }
@@ -266,22 +357,48 @@ hipError_t launch_weighted_sum(const ckks_ctx* c, u32 level, bool extended, cons
 
 // ---- out = sum of n <= KS_MAX_BATCH ciphertexts [2][level+1][N] (the accumulator's additions) ----------
 __global__ __launch_bounds__(PW_THREADS) void ct_sum_kernel(PtrList8 items, u32 n, u64* out,  // out may be one of the items
-                                                           
-                                                            const ModConst* __restrict__ mc, u32 N, u32 level) {
+                                                            const ModConst* __restrict__ mc, u32 N, u32 level, u32 limbs, u32 num_q) {
     const u32 x = blockIdx.x * PW_THREADS + threadIdx.x;
     if (x >= N) return;
     const u32 i = blockIdx.y, comp = blockIdx.z;
-    const u64 q = mc[i].q;
-    const size_t o = ((size_t)comp * (level + 1) + i) * N + x;
+    const u64 q = mc[i <= level ? i : num_q + (i - level - 1)].q;
+    const size_t o = ((size_t)comp * limbs + i) * N + x;
     u64 s = items.p[0][o];
     for (u32 b = 1; b < n; b++) s = add_mod(s, items.p[b][o], q);
     out[o] = s;
 }
 
-hipError_t launch_ct_sum(const ckks_ctx* c, u32 level, const PtrList8& items, u32 n, u64* out, hipStream_t st) {
-    dim3 grid((c->N + PW_THREADS - 1) / PW_THREADS, level + 1, 2);
-    ProfScope ps__(c, K_LINCOMB2, st, 16.0 * c->N * (level + 1.0) * (n + 1.0), 0.0);
-    hipLaunchKernelGGL(ct_sum_kernel, grid, dim3(PW_THREADS), 0, st, items, n, out, c->d_mc, c->N, level);
+// extended: the items are [2][level+1+k][N] on the basis Q_level P
+hipError_t launch_ct_sum(const ckks_ctx* c, u32 level, const PtrList8& items, u32 n, u64* out, hipStream_t st, bool extended) {
+    const u32 limbs = extended ? c->ext_limbs(level) : level + 1;
+    dim3 grid((c->N + PW_THREADS - 1) / PW_THREADS, limbs, 2);
+    ProfScope ps__(c, K_LINCOMB2, st, 16.0 * c->N * limbs * (n + 1.0), 0.0);
+    hipLaunchKernelGGL(ct_sum_kernel, grid, dim3(PW_THREADS), 0, st, items, n, out, c->d_mc, c->N, level, limbs, c->num_q);
+    return hipGetLastError();
+}
+
+// ---- out = P * ct on the extended basis Q_level P (zero on the special primes): a ciphertext that joins a sum
+// which is divided by P afterwards
+__global__ __launch_bounds__(PW_THREADS) void scale_p_ext_kernel(const u64* __restrict__ ct, u64* __restrict__ out,
+                                                                 const u64* __restrict__ negp, const ModConst* __restrict__ mc, u32 N,
+                                                                 u32 level, u32 E) {
+    const u32 x = blockIdx.x * PW_THREADS + threadIdx.x;
+    if (x >= N) return;
+    const u32 e = blockIdx.y, comp = blockIdx.z;
+    u64 r = 0;
+    if (e <= level) {
+        const ModConst m = mc[e];
+        r = mulmod_barrett(m.q - negp[e], ct[((size_t)comp * (level + 1) + e) * N + x], m);
+    }
+    out[((size_t)comp * E + e) * N + x] = r;
+}
+
+hipError_t launch_scale_p_ext(const ckks_ctx* c, u32 level, const u64* ct, u64* out, hipStream_t st) {
+    const u32 E = c->ext_limbs(level);
+    const u64* negp = c->d_moddown + 2 * c->k_pad + (size_t)c->k_pad * c->num_q + 2 * c->num_q;
+    dim3 grid((c->N + PW_THREADS - 1) / PW_THREADS, E, 2);
+    ProfScope ps__(c, K_MASK_MUL, st, 8.0 * c->N * (2.0 * (level + 1.0) + 2.0 * E), 2.0 * c->N * (level + 1.0));
+    hipLaunchKernelGGL(scale_p_ext_kernel, grid, dim3(PW_THREADS), 0, st, ct, out, negp, c->d_mc, c->N, level, E);
     return hipGetLastError();
 }
 

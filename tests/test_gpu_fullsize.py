@@ -220,9 +220,10 @@ def test_fc_batched_at_the_classifier_shape():
 
 def test_downsample_and_merge_at_the_block_group_transition():
     """Stage 2 -> stage 3 of the batched ResNet-20 at N = 2^16: two channel ciphertexts of 128 images of 16x16 (all N/2
-    slots) are compacted with stride 2 to 8x8 (8192 slots each), residues of both re-layouts against the oracle; four
-    such tiles of one channel (the same ciphertext at four stages of noise would do: here four different ones) are then
-    merged by the accumulator into a ciphertext of 512 images, checked in the slots."""
+    slots) are compacted with stride 2 to 8x8 (8192 slots each) in the configuration the benchmark times (divisions
+    deferred past the sums; 16 + 4 offsets inside the images, 32 + 4 over the images), residues of both re-layouts
+    against the oracle; four such tiles are then merged by the accumulator into a ciphertext of 512 images, checked in
+    the slots."""
     wl = CONFIGS["cfg5_resnet20_stage3"]
     p = wl.params()
     orc, ctx = Oracle(p), hx.Context(p)
@@ -232,7 +233,7 @@ def test_downsample_and_merge_at_the_block_group_transition():
     scale = 2.0 ** 40
     X = rng.uniform(-1, 1, (4, batch, height, width))
     cts = [orc.encrypt(X[t].reshape(-1), scale, level, s_ntt, 8010 + t) for t in range(4)]
-    plan = orc.downsample_plan(height, width, batch, r)
+    plan = orc.downsample_plan(height, width, batch, r, base=32, rows_per_group=2)
     offs = sorted({o for lo, hi, _ in plan for o in list(lo) + list(hi) if o % orc.n})
     keys = {o: orc.gen_rotation_key(s, s_ntt, o, 8100 + k) for k, o in enumerate(offs)}
     dkeys = {o: hx.ckks_key_load(ctx, hx.from_host(k), hx.ckks_galois_element(ctx, o)) for o, k in keys.items()}
@@ -240,10 +241,12 @@ def test_downsample_and_merge_at_the_block_group_transition():
     want = cts[:2]
     for stage, (lo, hi, slot_masks) in enumerate(plan):
         lv = level - stage
-        enc = [[None if m is None else orc.encode_ntt(m, float(p.moduli[lv]), lv) for m in row] for row in slot_masks]
+        ext = orc.ext_moduli_idx(lv)
+        enc = [[None if m is None else orc.lift_ntt(orc.encode(m, float(p.moduli[lv])), ext) for m in row] for row in slot_masks]
         cur = hx.he_relayout_two_rotations(ctx, cur, lv, lo, [dkeys.get(o) for o in lo], hi, [dkeys.get(o) for o in hi],
-                                           [[None if m is None else hx.from_host(m) for m in row] for row in enc])
-        want = [orc.relayout_two_rotations(ct, lv, lo, hi, enc, keys) for ct in want]      # the oracle follows two of the four
+                                           [[None if m is None else hx.from_host(m) for m in row] for row in enc],
+                                           schedule=hx.HE_RELAYOUT_DEFERRED)
+        want = [orc.relayout_two_rotations_deferred(ct, lv, lo, hi, enc, keys) for ct in want]   # the oracle follows two of the four
         for b in range(2):
             assert np.array_equal(hx.to_host(cur[b]), want[b]), f"stage {stage}, ciphertext {b}"
         del enc

@@ -425,7 +425,7 @@ def test_staged_keys_equal_the_oracle_keys_and_rotate():
 
 
 # ------------------------------------------------------------------- down-sampling compaction
-def run_downsample(orc, ctx, s, s_ntt, cts, level, plan, seed):
+def run_downsample(orc, ctx, s, s_ntt, cts, level, plan, seed, deferred=False):
     """Both stages of the plan on the GPU (channel vector at once) and in the oracle (one by one); returns (got, want)."""
     offs = sorted({r for lo, hi, _ in plan for r in list(lo) + list(hi) if r % orc.n})
     keys = {r: orc.gen_rotation_key(s, s_ntt, r, seed + k) for k, r in enumerate(offs)}
@@ -434,10 +434,16 @@ def run_downsample(orc, ctx, s, s_ntt, cts, level, plan, seed):
     want = [ct for ct in cts]
     for stage, (lo, hi, slot_masks) in enumerate(plan):
         lv = level - stage
-        enc = [[None if m is None else orc.encode_ntt(m, float(orc.moduli[lv]), lv) for m in row] for row in slot_masks]
+        if deferred:
+            ext = orc.ext_moduli_idx(lv)
+            enc = [[None if m is None else orc.lift_ntt(orc.encode(m, float(orc.moduli[lv])), ext) for m in row] for row in slot_masks]
+        else:
+            enc = [[None if m is None else orc.encode_ntt(m, float(orc.moduli[lv]), lv) for m in row] for row in slot_masks]
         cur = hx.he_relayout_two_rotations(ctx, cur, lv, lo, [dkeys.get(r) for r in lo], hi, [dkeys.get(r) for r in hi],
-                                           [[None if m is None else hx.from_host(m) for m in row] for row in enc])
-        want = [orc.relayout_two_rotations(ct, lv, lo, hi, enc, keys) for ct in want]
+                                           [[None if m is None else hx.from_host(m) for m in row] for row in enc],
+                                           schedule=hx.HE_RELAYOUT_DEFERRED if deferred else hx.HE_RELAYOUT_DIRECT)
+        ref = orc.relayout_two_rotations_deferred if deferred else orc.relayout_two_rotations
+        want = [ref(ct, lv, lo, hi, enc, keys) for ct in want]
         for b in range(len(cts)):
             assert np.array_equal(hx.to_host(cur[b]), want[b]), f"stage {stage}, ciphertext {b}"
     return [hx.to_host(t) for t in cur], want
@@ -468,6 +474,33 @@ def test_downsample_compaction_matches_oracle(height, width, batch, r, base, n_c
         assert np.abs(dec[:want.size] - want).max() < 1e-5 and np.abs(dec[want.size:]).max() < 1e-5
 
 
+@pytest.mark.parametrize("height,width,batch,r,base,group,n_ct", [(4, 4, 8, 2, 3, 1, 1), (4, 8, 5, 2, 5, 2, 3), (8, 8, 2, 2, 1, 4, 10),
+                                                                  (2, 2, 40, 2, 2, 1, 2)])
+def test_downsample_compaction_deferred_matches_oracle(height, width, batch, r, base, group, n_ct):
+    """The schedule with the divisions by P after the sums: residues of both stages against the oracle's deferred
+    re-layout, slots against numpy slicing.  Several rows per group (16 first rotations, no second one inside the
+    images), base = batch (only first rotations over the images), 20 second rotations (summed in two launches),
+    ten ciphertexts (two channel batches)."""
+    p = make_params(10, 5, 2, 3)
+    orc, ctx = both(p)
+    level = p.num_q - 1
+    s, s_ntt = orc.gen_secret(620)
+    rng = np.random.default_rng(621)
+    scale = 2.0 ** 40
+    X = rng.uniform(-1, 1, (n_ct, batch, height, width))
+    cts = []
+    for c in range(n_ct):
+        z = rng.uniform(-1, 1, orc.n)
+        z[:batch * height * width] = X[c].reshape(-1)
+        cts.append(orc.encrypt(z, scale, level, s_ntt, 630 + c))
+    plan = orc.downsample_plan(height, width, batch, r, base, rows_per_group=group)
+    got, _ = run_downsample(orc, ctx, s, s_ntt, cts, level, plan, 670, deferred=True)
+    for c in range(n_ct):
+        dec = orc.decrypt(got[c], level - 2, s_ntt, scale)
+        want = X[c][:, ::r, ::r].reshape(-1)
+        assert np.abs(dec[:want.size] - want).max() < 1e-5 and np.abs(dec[want.size:]).max() < 1e-5
+
+
 def test_relayout_rejects_bad_arguments():
     p = make_params(10, 5, 2, 3)
     orc, ctx = both(p)
@@ -485,9 +518,12 @@ def test_relayout_rejects_bad_arguments():
         hx.he_relayout_two_rotations(ctx, [hx.empty(2, 1, orc.N)], 0, [0], [None], [0], [None], [[hx.empty(1, orc.N)]],
                                      outs=[hx.empty(0)])
     assert e.value.code == hx.binding.CKKS_ERR_LEVEL_MISMATCH
-    with pytest.raises(hx.CkksError) as e:
-        hx.he_relayout_two_rotations(ctx, [ct], level, [0, 4], [None, key], [0], [None], [[m, m]], ws=hx.empty(512))
-    assert e.value.code == hx.binding.CKKS_ERR_WORKSPACE_TOO_SMALL
+    for schedule, mm in ((hx.HE_RELAYOUT_DIRECT, m), (hx.HE_RELAYOUT_DEFERRED, hx.empty(level + 1 + p.num_p, orc.N))):
+        with pytest.raises(hx.CkksError) as e:
+            hx.he_relayout_two_rotations(ctx, [ct], level, [0, 4], [None, key], [0], [None], [[mm, mm]], schedule=schedule, ws=hx.empty(512))
+        assert e.value.code == hx.binding.CKKS_ERR_WORKSPACE_TOO_SMALL
+    with pytest.raises(ValueError):                         # masks of the other schedule's shape
+        hx.he_relayout_two_rotations(ctx, [ct], level, [0, 4], [None, key], [0], [None], [[m, m]], schedule=hx.HE_RELAYOUT_DEFERRED)
 
 
 # ------------------------------------------------------------------------------------ activation
