@@ -537,7 +537,8 @@ __global__ __launch_bounds__(KS_THREADS) void moddown_conv_kernel(const u64* __r
     }
 }
 
-template <int KP>
+// KP: padded row length of the tables; KR: how many of the row's entries are real (the rest are zeros that need no arithmetic)
+template <int KP, int KR = KP>
 __global__ __launch_bounds__(KS_THREADS) void moddown_conv50_kernel(const u64* __restrict__ v, u64* __restrict__ w,
                                                                     const u64* __restrict__ tab, const ModConst* __restrict__ mc,
                                                                     u32 N, u32 level, u32 num_q, u32 k, u32 E, u32 first, u32 n_out,
@@ -545,10 +546,10 @@ __global__ __launch_bounds__(KS_THREADS) void moddown_conv50_kernel(const u64* _
     const u32 x = blockIdx.x * KS_THREADS + threadIdx.x;
     if (x >= N) return;
     const u32 comp = blockIdx.z;
-    Split50 z[KP];
+    Split50 z[KR];
     u32 n_neg = 0;
 #pragma unroll
-    for (u32 a = 0; a < KP; a++) {
+    for (u32 a = 0; a < KR; a++) {
         z[a] = {0, 0, 0};
         if (a < k) {
             const u64 pa = mc[dropped_modulus(a, level, num_q, merged)].q;
@@ -568,7 +569,7 @@ __global__ __launch_bounds__(KS_THREADS) void moddown_conv50_kernel(const u64* _
         for (u32 a = 0; a < KP; a++) cv[a] = pe[a];
         Acc50 acc = {0, 0, 0};
 #pragma unroll
-        for (u32 a = 0; a < KP; a++) acc50_mad(acc, z[a], split50(cv[a]));
+        for (u32 a = 0; a < KR; a++) acc50_mad(acc, z[a], split50(cv[a]));
         U128 s = acc50_value(acc);
         acc_wide(s, n_neg, negp[i]);
         w[((size_t)comp * n_out + i) * N + x] = barrett_reduce(s, mc[i]);
@@ -586,6 +587,8 @@ hipError_t launch_moddown_conv(const ckks_ctx* c, u32 level, bool merged, const 
             hipLaunchKernelGGL(moddown_conv50_kernel<4>, grid, dim3(KS_THREADS), 0, st, v, w, tab, c->d_mc, c->N, level, c->num_q, k, E, first, n_out, merged);
         else if (kp == 8)
             hipLaunchKernelGGL(moddown_conv50_kernel<8>, grid, dim3(KS_THREADS), 0, st, v, w, tab, c->d_mc, c->N, level, c->num_q, k, E, first, n_out, merged);
+        else if (kp == 12 && k == 9)
+            hipLaunchKernelGGL((moddown_conv50_kernel<12, 9>), grid, dim3(KS_THREADS), 0, st, v, w, tab, c->d_mc, c->N, level, c->num_q, k, E, first, n_out, merged);
         else if (kp == 12)
             hipLaunchKernelGGL(moddown_conv50_kernel<12>, grid, dim3(KS_THREADS), 0, st, v, w, tab, c->d_mc, c->N, level, c->num_q, k, E, first, n_out, merged);
         else
