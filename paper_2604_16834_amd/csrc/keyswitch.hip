@@ -28,7 +28,7 @@ __device__ __forceinline__ u32 galois_gather_index(u32 k, u32 g, u32 log_n) {
 // y     [nd][N]      digit limbs in coefficient form (canonical)
 // c_in  [level+1][N] the polynomial being switched, NTT form (source of the digit's own limbs)
 // digit [E][N]       out: own limbs copied (NTT form), other limbs in coefficient form
-#define MODUP_LIMBS_PER_BLOCK 16
+#define MODUP_LIMBS_PER_BLOCK 32
 __global__ __launch_bounds__(KS_THREADS) void modup_conv_kernel(const u64* __restrict__ y, size_t y_bstride, PtrList8 c_list,
                                                                 u64* __restrict__ digit, size_t digit_bstride,
                                                                 const u64* __restrict__ tab, const ModConst* __restrict__ mc, u32 N,
