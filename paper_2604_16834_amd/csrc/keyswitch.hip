@@ -28,11 +28,10 @@ __device__ __forceinline__ u32 galois_gather_index(u32 k, u32 g, u32 log_n) {
 // y     [nd][N]      digit limbs in coefficient form (canonical)
 // c_in  [level+1][N] the polynomial being switched, NTT form (source of the digit's own limbs)
 // digit [E][N]       out: own limbs copied (NTT form), other limbs in coefficient form
-#define MODUP_LIMBS_PER_BLOCK 32
 __global__ __launch_bounds__(KS_THREADS) void modup_conv_kernel(const u64* __restrict__ y, size_t y_bstride, PtrList8 c_list,
                                                                 u64* __restrict__ digit, size_t digit_bstride,
                                                                 const u64* __restrict__ tab, const ModConst* __restrict__ mc, u32 N,
-                                                                u32 level, u32 num_q, u32 lo, u32 nd, u32 alpha, u32 M, u32 E) {
+                                                                u32 level, u32 num_q, u32 lo, u32 nd, u32 alpha, u32 M, u32 E, u32 lpb) {
     const u32 x = blockIdx.x * KS_THREADS + threadIdx.x;
     if (x >= N) return;
     y += blockIdx.z * y_bstride;
@@ -48,8 +47,8 @@ __global__ __launch_bounds__(KS_THREADS) void modup_conv_kernel(const u64* __res
             n_neg += yv[a] > (qa >> 1) ? 1 : 0;
         }
     const u64* negq = tab + (size_t)alpha * (2 + M);  // alpha = padded row length here
-    const u32 e0 = blockIdx.y * MODUP_LIMBS_PER_BLOCK;
-    for (u32 e = e0; e < e0 + MODUP_LIMBS_PER_BLOCK && e < E; e++) {
+    const u32 e0 = blockIdx.y * lpb;
+    for (u32 e = e0; e < e0 + lpb && e < E; e++) {
         const u32 t = e <= level ? e : num_q + (e - level - 1);
         if (t >= lo && t < lo + nd) {
             digit[(size_t)e * N + x] = c_in[(size_t)t * N + x];
@@ -70,7 +69,7 @@ template <int AP>
 __global__ __launch_bounds__(KS_THREADS) void modup_conv50_kernel(const u64* __restrict__ y, size_t y_bstride, PtrList8 c_list,
                                                                   u64* __restrict__ digit, size_t digit_bstride,
                                                                   const u64* __restrict__ tab, const ModConst* __restrict__ mc, u32 N,
-                                                                  u32 level, u32 num_q, u32 lo, u32 nd, u32 M, u32 E) {
+                                                                  u32 level, u32 num_q, u32 lo, u32 nd, u32 M, u32 E, u32 lpb) {
     const u32 x = blockIdx.x * KS_THREADS + threadIdx.x;
     if (x >= N) return;
     y += blockIdx.z * y_bstride;
@@ -90,8 +89,8 @@ __global__ __launch_bounds__(KS_THREADS) void modup_conv50_kernel(const u64* __r
     }
     const u64* conv = (const u64*)__builtin_assume_aligned(tab + 2 * AP, 8 * AP);
     const u64* negq = tab + (size_t)AP * (2 + M);
-    const u32 e0 = blockIdx.y * MODUP_LIMBS_PER_BLOCK;
-    for (u32 e = e0; e < e0 + MODUP_LIMBS_PER_BLOCK && e < E; e++) {
+    const u32 e0 = blockIdx.y * lpb;
+    for (u32 e = e0; e < e0 + lpb && e < E; e++) {
         const u32 t = e <= level ? e : num_q + (e - level - 1);
         if (t >= lo && t < lo + nd) {
             digit[(size_t)e * N + x] = c_in[(size_t)t * N + x];
@@ -114,19 +113,23 @@ __global__ __launch_bounds__(KS_THREADS) void modup_conv50_kernel(const u64* __r
 hipError_t launch_modup_conv(const ckks_ctx* c, u32 level, u32 j, const u64* y, size_t y_bstride, const PtrList8& c_in, u64* digit,
                              size_t digit_bstride, u32 n, hipStream_t st) {
     const u32 E = c->ext_limbs(level), lo = c->digit_lo(j), nd = c->digit_hi(j, level) - lo;
-    dim3 grid((c->N + KS_THREADS - 1) / KS_THREADS, (E + MODUP_LIMBS_PER_BLOCK - 1) / MODUP_LIMBS_PER_BLOCK, n);
+    // target limbs per thread: the digit's prepared residues are reused for all of them, but a small batch needs the
+    // limbs spread over more workgroups to fill the chip
+    const u32 x_wgs = (c->N + KS_THREADS - 1) / KS_THREADS;
+    const u32 lpb = x_wgs * n >= 1024 ? 32 : (x_wgs * n >= 512 ? 8 : 4);
+    dim3 grid(x_wgs, (E + lpb - 1) / lpb, n);
     const u64* tab = c->modup_table(level, j);
     ProfScope ps__(c, K_MODUP_CONV, st, 8.0 * n * c->N * (2.0 * nd + E), (double)n * c->N * nd * (1.0 + E - nd));
     if (c->small_q) {
         if (c->alpha_pad == 4)
-            hipLaunchKernelGGL(modup_conv50_kernel<4>, grid, dim3(KS_THREADS), 0, st, y, y_bstride, c_in, digit, digit_bstride, tab, c->d_mc, c->N, level, c->num_q, lo, nd, c->M, E);
+            hipLaunchKernelGGL(modup_conv50_kernel<4>, grid, dim3(KS_THREADS), 0, st, y, y_bstride, c_in, digit, digit_bstride, tab, c->d_mc, c->N, level, c->num_q, lo, nd, c->M, E, lpb);
         else if (c->alpha_pad == 8)
-            hipLaunchKernelGGL(modup_conv50_kernel<8>, grid, dim3(KS_THREADS), 0, st, y, y_bstride, c_in, digit, digit_bstride, tab, c->d_mc, c->N, level, c->num_q, lo, nd, c->M, E);
+            hipLaunchKernelGGL(modup_conv50_kernel<8>, grid, dim3(KS_THREADS), 0, st, y, y_bstride, c_in, digit, digit_bstride, tab, c->d_mc, c->N, level, c->num_q, lo, nd, c->M, E, lpb);
         else
-            hipLaunchKernelGGL(modup_conv50_kernel<16>, grid, dim3(KS_THREADS), 0, st, y, y_bstride, c_in, digit, digit_bstride, tab, c->d_mc, c->N, level, c->num_q, lo, nd, c->M, E);
+            hipLaunchKernelGGL(modup_conv50_kernel<16>, grid, dim3(KS_THREADS), 0, st, y, y_bstride, c_in, digit, digit_bstride, tab, c->d_mc, c->N, level, c->num_q, lo, nd, c->M, E, lpb);
     } else {
         hipLaunchKernelGGL(modup_conv_kernel, grid, dim3(KS_THREADS), 0, st, y, y_bstride, c_in, digit, digit_bstride, tab, c->d_mc,
-                           c->N, level, c->num_q, lo, nd, c->alpha_pad, c->M, E);
+                           c->N, level, c->num_q, lo, nd, c->alpha_pad, c->M, E, lpb);
     }
     return hipGetLastError();
 }
@@ -501,7 +504,6 @@ hipError_t launch_key_inner_taps(const ckks_ctx* c, u32 level, const u64* digits
 
 // ---- ModDown, conversion of the P-part ----------------------------------------------------------
 // v [2][E][N]: limbs level+1.. hold the P-part in coefficient form.  w [2][level+1][N] (coefficients)
-#define MODDOWN_LIMBS_PER_BLOCK 12
 // Dropped limbs: positions first..first+k-1 of v's E limbs; their moduli: `merged` ? (q_level, p_0, ...) : (p_0, ...).
 // Results on limbs 0..n_out-1 (n_out = level+1, or level when merged).
 __device__ __forceinline__ u32 dropped_modulus(u32 a, u32 level, u32 num_q, bool merged) {
@@ -511,7 +513,7 @@ __device__ __forceinline__ u32 dropped_modulus(u32 a, u32 level, u32 num_q, bool
 __global__ __launch_bounds__(KS_THREADS) void moddown_conv_kernel(const u64* __restrict__ v, u64* __restrict__ w,
                                                                   const u64* __restrict__ tab, const ModConst* __restrict__ mc,
                                                                   u32 N, u32 level, u32 num_q, u32 k, u32 kp, u32 E, u32 first,
-                                                                  u32 n_out, bool merged) {
+                                                                  u32 n_out, bool merged, u32 lpb) {
     const u32 x = blockIdx.x * KS_THREADS + threadIdx.x;
     if (x >= N) return;
     const u32 comp = blockIdx.z;
@@ -526,8 +528,8 @@ __global__ __launch_bounds__(KS_THREADS) void moddown_conv_kernel(const u64* __r
         }
     const u64* phat_q = tab + 2 * kp;  // [num_q][kp]
     const u64* negp = tab + 2 * kp + (size_t)kp * num_q + 2 * num_q;
-    const u32 i0 = blockIdx.y * MODDOWN_LIMBS_PER_BLOCK;
-    for (u32 i = i0; i < i0 + MODDOWN_LIMBS_PER_BLOCK && i < n_out; i++) {
+    const u32 i0 = blockIdx.y * lpb;
+    for (u32 i = i0; i < i0 + lpb && i < n_out; i++) {
         U128 acc = {0, 0};
 #pragma unroll
         for (u32 a = 0; a < KS_MAX_DIGIT; a++)
@@ -542,7 +544,7 @@ template <int KP, int KR = KP>
 __global__ __launch_bounds__(KS_THREADS) void moddown_conv50_kernel(const u64* __restrict__ v, u64* __restrict__ w,
                                                                     const u64* __restrict__ tab, const ModConst* __restrict__ mc,
                                                                     u32 N, u32 level, u32 num_q, u32 k, u32 E, u32 first, u32 n_out,
-                                                                    bool merged) {
+                                                                    bool merged, u32 lpb) {
     const u32 x = blockIdx.x * KS_THREADS + threadIdx.x;
     if (x >= N) return;
     const u32 comp = blockIdx.z;
@@ -561,8 +563,8 @@ __global__ __launch_bounds__(KS_THREADS) void moddown_conv50_kernel(const u64* _
     constexpr int ROW_ALIGN = (KP & (KP - 1)) == 0 ? 8 * KP : 32;  // rows of 12 words are 32-byte aligned
     const u64* phat_q = (const u64*)__builtin_assume_aligned(tab + 2 * KP, ROW_ALIGN);  // [num_q][KP]
     const u64* negp = tab + 2 * KP + (size_t)KP * num_q + 2 * num_q;
-    const u32 i0 = blockIdx.y * MODDOWN_LIMBS_PER_BLOCK;
-    for (u32 i = i0; i < i0 + MODDOWN_LIMBS_PER_BLOCK && i < n_out; i++) {
+    const u32 i0 = blockIdx.y * lpb;
+    for (u32 i = i0; i < i0 + lpb && i < n_out; i++) {
         const u64* pe = (const u64*)__builtin_assume_aligned(phat_q + (size_t)i * KP, ROW_ALIGN);
         u64 cv[KP];
 #pragma unroll
@@ -580,22 +582,24 @@ hipError_t launch_moddown_conv(const ckks_ctx* c, u32 level, bool merged, const 
     const u32 n_out = merged ? level : level + 1, k = merged ? c->num_p + 1 : c->num_p, kp = merged ? c->k2_pad : c->k_pad;
     const u32 first = merged ? level : level + 1, E = c->ext_limbs(level);
     const u64* tab = merged ? c->moddown_rs_table(level) : c->d_moddown;
-    dim3 grid((c->N + KS_THREADS - 1) / KS_THREADS, (n_out + MODDOWN_LIMBS_PER_BLOCK - 1) / MODDOWN_LIMBS_PER_BLOCK, batch);
+    const u32 x_wgs = (c->N + KS_THREADS - 1) / KS_THREADS;
+    const u32 lpb = x_wgs * batch >= 2048 ? 12 : 6;  // as in launch_modup_conv
+    dim3 grid(x_wgs, (n_out + lpb - 1) / lpb, batch);
     ProfScope ps__(c, K_MODDOWN_CONV, st, 8.0 * batch * c->N * (k + n_out), 1.0 * batch * c->N * k * (n_out + 1.0));
     if (c->small_q) {
         if (kp == 4)
-            hipLaunchKernelGGL(moddown_conv50_kernel<4>, grid, dim3(KS_THREADS), 0, st, v, w, tab, c->d_mc, c->N, level, c->num_q, k, E, first, n_out, merged);
+            hipLaunchKernelGGL(moddown_conv50_kernel<4>, grid, dim3(KS_THREADS), 0, st, v, w, tab, c->d_mc, c->N, level, c->num_q, k, E, first, n_out, merged, lpb);
         else if (kp == 8)
-            hipLaunchKernelGGL(moddown_conv50_kernel<8>, grid, dim3(KS_THREADS), 0, st, v, w, tab, c->d_mc, c->N, level, c->num_q, k, E, first, n_out, merged);
+            hipLaunchKernelGGL(moddown_conv50_kernel<8>, grid, dim3(KS_THREADS), 0, st, v, w, tab, c->d_mc, c->N, level, c->num_q, k, E, first, n_out, merged, lpb);
         else if (kp == 12 && k == 9)
-            hipLaunchKernelGGL((moddown_conv50_kernel<12, 9>), grid, dim3(KS_THREADS), 0, st, v, w, tab, c->d_mc, c->N, level, c->num_q, k, E, first, n_out, merged);
+            hipLaunchKernelGGL((moddown_conv50_kernel<12, 9>), grid, dim3(KS_THREADS), 0, st, v, w, tab, c->d_mc, c->N, level, c->num_q, k, E, first, n_out, merged, lpb);
         else if (kp == 12)
-            hipLaunchKernelGGL(moddown_conv50_kernel<12>, grid, dim3(KS_THREADS), 0, st, v, w, tab, c->d_mc, c->N, level, c->num_q, k, E, first, n_out, merged);
+            hipLaunchKernelGGL(moddown_conv50_kernel<12>, grid, dim3(KS_THREADS), 0, st, v, w, tab, c->d_mc, c->N, level, c->num_q, k, E, first, n_out, merged, lpb);
         else
-            hipLaunchKernelGGL(moddown_conv50_kernel<16>, grid, dim3(KS_THREADS), 0, st, v, w, tab, c->d_mc, c->N, level, c->num_q, k, E, first, n_out, merged);
+            hipLaunchKernelGGL(moddown_conv50_kernel<16>, grid, dim3(KS_THREADS), 0, st, v, w, tab, c->d_mc, c->N, level, c->num_q, k, E, first, n_out, merged, lpb);
         return hipGetLastError();
     }
-    hipLaunchKernelGGL(moddown_conv_kernel, grid, dim3(KS_THREADS), 0, st, v, w, tab, c->d_mc, c->N, level, c->num_q, k, kp, E, first, n_out, merged);
+    hipLaunchKernelGGL(moddown_conv_kernel, grid, dim3(KS_THREADS), 0, st, v, w, tab, c->d_mc, c->N, level, c->num_q, k, kp, E, first, n_out, merged, lpb);
     return hipGetLastError();
 }
 
