@@ -117,6 +117,22 @@ int run_modup(const ckks_ctx* c, u32 level, const u64* const* srcs, u32 n, const
     return CKKS_OK;
 }
 
+// What the forward transform of the converted dropped part does to its results instead of storing them (see FwdEpilogue).
+FwdEpilogue moddown_epilogue(const ckks_ctx* c, u32 level, bool merged, const u64* v, const FinalItem* items, u32 n) {
+    FwdEpilogue ep;
+    const u32 kp = merged ? c->k2_pad : c->k_pad;
+    const u64* tab = merged ? c->moddown_rs_table(level) : c->d_moddown;
+    ep.v = v;
+    ep.cinv = tab + 2 * kp + (size_t)kp * c->num_q;
+    ep.mci = c->d_mc;
+    ep.E = c->ext_limbs(level);
+    ep.n_out = merged ? level : level + 1;
+    ep.num_q = c->num_q;
+    ep.pad = 0;
+    for (u32 r = 0; r < KS_MAX_BATCH; r++) ep.B.it[r] = r < n ? items[r] : FinalItem{nullptr, nullptr, nullptr, nullptr, 1, 0};
+    return ep;
+}
+
 // ModDown of the n inner products sitting in ws.v: one pass of each kernel over the whole batch.
 // items[r] says what is added to / multiplied into the r-th result and where it goes ([2][level+1][N]).
 // merged: the division is by P*q_level (ModDown and rescale in one): the dropped limbs are position
@@ -129,12 +145,22 @@ int run_moddown(const ckks_ctx* c, u32 level, const KsWs& ws, u32 n, const Final
         for (u32 a = 1; a <= k; a++) dl.mod[a] = (unsigned char)(c->num_q + a - 1);
         HIP_TRY(launch_ntt(c, true, ws.v, E, ws.v, E, dl, 2 * n, st));
         HIP_TRY(launch_moddown_conv(c, level, true, ws.v, ws.w, 2 * n, st));
+        if (ntt_has_epilogue(c)) {  // the last step rides on the transform's stores
+            const FwdEpilogue ep = moddown_epilogue(c, level, true, ws.v, items, n);
+            HIP_TRY(launch_ntt(c, false, ws.w, level, ws.w, level, range_list(0, level, 0), 2 * n, st, nullptr, &ep));
+            return CKKS_OK;
+        }
         HIP_TRY(launch_ntt(c, false, ws.w, level, ws.w, level, range_list(0, level, 0), 2 * n, st));
         HIP_TRY(launch_moddown_final(c, level, true, ws.v, ws.w, items, n, st));
         return CKKS_OK;
     }
     HIP_TRY(launch_ntt(c, true, ws.v, E, ws.v, E, range_list(L1, k, c->num_q), 2 * n, st));  // P-part -> coefficients
     HIP_TRY(launch_moddown_conv(c, level, false, ws.v, ws.w, 2 * n, st));
+    if (ntt_has_epilogue(c)) {
+        const FwdEpilogue ep = moddown_epilogue(c, level, false, ws.v, items, n);
+        HIP_TRY(launch_ntt(c, false, ws.w, L1, ws.w, L1, range_list(0, L1, 0), 2 * n, st, nullptr, &ep));
+        return CKKS_OK;
+    }
     HIP_TRY(launch_ntt(c, false, ws.w, L1, ws.w, L1, range_list(0, L1, 0), 2 * n, st));
     HIP_TRY(launch_moddown_final(c, level, false, ws.v, ws.w, items, n, st));
     return CKKS_OK;

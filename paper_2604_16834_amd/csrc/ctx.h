@@ -86,6 +86,16 @@ struct FinalItem {
 struct FinalBatch {
     FinalItem it[KS_MAX_BATCH];
 };
+// The last step of a division by dropped moduli (ModDown, or ModDown merged with the rescale), applied by the forward
+// transform itself as it stores its results w (batch item 2r + comp, limb i) instead of writing them:
+//   out_r[comp][i] = ((v[2r+comp][i] - w) * cinv[i] + addend) * mask      (addend, mask as in FinalItem)
+struct FwdEpilogue {
+    const u64* v;         // [batch][E][N]
+    const u64* cinv;      // the multiplier per limb, its Shoup companion at cinv[num_q + i]
+    const ModConst* mci;  // integer constants per modulus
+    u32 E, n_out, num_q, pad;
+    FinalBatch B;
+};
 
 struct ckks_key {
     const u64* d_key;
@@ -162,7 +172,10 @@ struct ProfScope {
 // ntt.hip: batch x pl.n limb-polys; item b reads src + b*src_bstride*N (or src_ptrs[b] when given: host
 // array of `batch` <= KS_MAX_BATCH device pointers) and writes dst + b*dst_bstride*N
 hipError_t launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, size_t src_bstride, u64* dst,
-                      size_t dst_bstride, const PolyList& pl, u32 batch, hipStream_t st, const u64* const* src_ptrs = nullptr);
+                      size_t dst_bstride, const PolyList& pl, u32 batch, hipStream_t st, const u64* const* src_ptrs = nullptr,
+                      const FwdEpilogue* epilogue = nullptr);
+// whether launch_ntt can apply an epilogue in this ring (it needs the two-pass transform)
+inline bool ntt_has_epilogue(const ckks_ctx* c) { return c->log_n > CKKS_TILE_LOG; }
 // keyswitch.hip
 hipError_t launch_modup_conv(const ckks_ctx* c, u32 level, u32 j, const u64* y, size_t y_bstride, const PtrList8& c_in, u64* digit,
                              size_t digit_bstride, u32 n, hipStream_t st);

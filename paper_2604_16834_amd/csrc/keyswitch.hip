@@ -13,16 +13,10 @@
 //              u[i] = (v[q_i] - w[i]) * P^-1  (+ an optional addend)
 // Sums of products are accumulated unreduced in 128 bits and reduced once.
 #include "ctx.h"
+#include "galois.h"
 
 #define KS_THREADS 256
 #define KS_MAX_DIGIT 16  // limbs per digit / special primes handled in registers
-
-__device__ __forceinline__ u32 galois_gather_index(u32 k, u32 g, u32 log_n) {
-    // evaluation point of entry k is psi^(2*brv(k)+1); sigma_g reads the entry whose point is that
-    // power times g
-    u32 e = ((2u * (__brev(k) >> (32 - log_n)) + 1u) * g) & ((2u << log_n) - 1u);
-    return __brev((e - 1u) >> 1) >> (32 - log_n);
-}
 
 // ---- ModUp: basis extension of one digit --------------------------------------------------------
 // y     [nd][N]      digit limbs in coefficient form (canonical)

@@ -30,6 +30,7 @@
 //             all arithmetic is exact.  Between the two passes the data sit in HBM as doubles.
 // Rings below 2^11 use a plain one-tile integer kernel.
 #include "ctx.h"
+#include "galois.h"
 
 #pragma clang fp contract(off)  // the error-free transformations below need every product and sum as written
 
@@ -255,8 +256,8 @@ __device__ __forceinline__ u64* item_dst(const NttArgs& args, const PolyList& pl
     return args.dst + (((size_t)b * args.dst_bstride + pl.dpos[a]) << args.log_n);
 }
 
-template <class A, int IT>
-__global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_kernel(NttArgs args, PolyList pl) {
+template <class A, int IT, bool EPI>
+__device__ __forceinline__ void fwd_lo_body(const NttArgs& args, const PolyList& pl, const FwdEpilogue& ep) {
     typedef typename A::E E;
     __shared__ E lds0[LDS_PADDED_WORDS];
     __shared__ E lds1[LDS_PADDED_WORDS];
@@ -322,6 +323,12 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_kernel(NttArgs args, P
         __syncthreads();
 #pragma unroll
         for (int j = 0; j < 8; j++) v[j] = buf0[LDS_PAD(8 * tid + j)];
+        u64 vv[8];
+        if (EPI) {  // what the results are subtracted from: requested now, needed after the last round
+            const u64* vrow = ep.v + (((size_t)(b0 + it) * ep.E + pl.dpos[tile.a]) << args.log_n) + off;
+#pragma unroll
+            for (int j = 0; j < 8; j++) vv[j] = vrow[tid + 256 * j];
+        }
         fwd_rows_pre<A, 2>(v, wd, P.mc);
         fwd_rows_pre<A, 2>(v + 4, wd + 3, P.mc);
         A::fwd_round_end(v, P.mc);
@@ -329,10 +336,45 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_kernel(NttArgs args, P
 #pragma unroll
         for (int j = 0; j < 8; j++) buf1[LDS_PAD(8 * tid + j)] = v[j];
         __syncthreads();
-        u64* dst = item_dst(args, pl, b0 + it, tile.a) + off;
+        if (!EPI) {
+            u64* dst = item_dst(args, pl, b0 + it, tile.a) + off;
 #pragma unroll
-        for (int j = 0; j < 8; j++) dst[tid + 256 * j] = A::store_fwd_final(buf1[LDS_PAD(tid + 256 * j)], P.mc);
+            for (int j = 0; j < 8; j++) dst[tid + 256 * j] = A::store_fwd_final(buf1[LDS_PAD(tid + 256 * j)], P.mc);
+        } else {
+            // the division's last step on the results w, which are not stored: out = ((v - w) * cinv + addend) * mask
+            const u32 i = pl.dpos[tile.a], bb = b0 + it, comp = bb & 1;
+            const FinalItem fi = ep.B.it[bb >> 1];
+            const ModConst mi = ep.mci[pl.mod[tile.a]];
+            const u64 cv = ep.cinv[i], cvs = ep.cinv[ep.num_q + i];
+            const u64* add = comp ? fi.add1 : fi.add0;
+            u64* orow = fi.out + (((size_t)comp * ep.n_out + i) << args.log_n) + off;
+#pragma unroll
+            for (int j = 0; j < 8; j++) {
+                const u32 p = tid + 256 * j;
+                const u64 w = A::store_fwd_final(buf1[LDS_PAD(p)], P.mc);
+                u64 r = mul_shoup(sub_mod(vv[j], w, mi.q), cv, cvs, mi.q);
+                if (add) {
+                    const u32 x = (u32)off + p;
+                    const u32 xs = fi.g == 1 ? x : galois_gather_index(x, fi.g, args.log_n);
+                    r = add_mod(r, add[((size_t)i << args.log_n) + xs], mi.q);
+                }
+                if (fi.mask) r = mulmod_barrett(r, fi.mask[((size_t)i << args.log_n) + off + p], mi);
+                orow[p] = r;
+            }
+        }
     }
+}
+
+template <class A, int IT>
+__global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_kernel(NttArgs args, PolyList pl) {
+    FwdEpilogue none;  // never read
+    fwd_lo_body<A, IT, false>(args, pl, none);
+}
+
+// the lo pass as the last kernel of a division by dropped moduli
+template <class A, int IT>
+__global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_div_kernel(NttArgs args, PolyList pl, FwdEpilogue ep) {
+    fwd_lo_body<A, IT, true>(args, pl, ep);
 }
 
 template <class A, int IT>
@@ -553,15 +595,22 @@ static void launch_lo_it(bool inverse, dim3 grid, hipStream_t st, const NttArgs&
     else hipLaunchKernelGGL((ntt_fwd_lo_kernel<A, IT>), grid, dim3(NTT_THREADS), 0, st, args, pl);
 }
 template <class A>
+static void launch_lo_div(u32 items, dim3 grid, hipStream_t st, const NttArgs& args, const PolyList& pl, const FwdEpilogue& ep) {
+    if (items == 2) hipLaunchKernelGGL((ntt_fwd_lo_div_kernel<A, 2>), grid, dim3(NTT_THREADS), 0, st, args, pl, ep);
+    else hipLaunchKernelGGL((ntt_fwd_lo_div_kernel<A, 1>), grid, dim3(NTT_THREADS), 0, st, args, pl, ep);
+}
+template <class A>
 static void launch_lo(bool inverse, u32 items, dim3 grid, hipStream_t st, const NttArgs& args, const PolyList& pl) {
     if (items == 2) launch_lo_it<A, 2>(inverse, grid, st, args, pl);
     else launch_lo_it<A, 1>(inverse, grid, st, args, pl);
 }
 
 hipError_t launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, size_t src_bstride, u64* dst,
-                      size_t dst_bstride, const PolyList& pl, u32 batch, hipStream_t st, const u64* const* src_ptrs) {
+                      size_t dst_bstride, const PolyList& pl, u32 batch, hipStream_t st, const u64* const* src_ptrs,
+                      const FwdEpilogue* epilogue) {
     if (pl.n == 0 || batch == 0) return hipSuccess;
     if (src_ptrs && batch > KS_MAX_BATCH) return hipErrorInvalidValue;
+    if (epilogue && (inverse || !ntt_has_epilogue(c) || batch > 2 * KS_MAX_BATCH)) return hipErrorInvalidValue;
     const bool f64 = c->ntt_f64;
     NttArgs args;
     args.src = src;
@@ -614,7 +663,14 @@ hipError_t launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, size_t sr
         if (c->log_hi > 0) {
             args.last = 0;
             { ProfScope ps__(c, K_NTT_FWD_HI, st, pass_bytes, hi_ops); hi(args, pl); }
-            { ProfScope ps__(c, K_NTT_FWD_LO, st, pass_bytes, lo_ops); lo(second, pd); }
+            if (epilogue) {  // reads w and v, writes the quotients (plus the addends it reads)
+                ProfScope ps__(c, K_NTT_FWD_LO, st, 1.5 * pass_bytes, lo_ops);
+                if (f64) launch_lo_div<ArithF64>(lo_items, grid_lo, st, second, pd, *epilogue);
+                else launch_lo_div<ArithU64>(lo_items, grid_lo, st, second, pd, *epilogue);
+            } else {
+                ProfScope ps__(c, K_NTT_FWD_LO, st, pass_bytes, lo_ops);
+                lo(second, pd);
+            }
         } else {
             ProfScope ps__(c, K_NTT_FWD_LO, st, pass_bytes, lo_ops);
             lo(args, pl);
