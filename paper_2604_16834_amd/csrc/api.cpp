@@ -276,12 +276,18 @@ int conv_deferred(const ckks_ctx* c, const he_conv_desc* d, const u32* gs, const
         int rc = run_modup(c, level, c1s, n, ws, st);
         if (rc) return rc;
         // taps without a rotation (the centre) are a product with the mask; all the others go through one launch
-        const u64 *tkeys[8], *tmasks[8];
-        u32 tg[8], ttap[8], n_taps = 0;
+        const u64 *tkeys[8], *tmasks[8], *centre_mask = nullptr;
+        u32 tg[8], ttap[8], n_taps = 0, centre_tap = 0, n_centre = 0;
+        for (u32 t = 0; t < 9; t++) n_centre += gs[t] == 1 ? 1 : 0;
         for (u32 t = 0; t < 9; t++) {
             const u64* mask = masks + (size_t)t * E * N;
             if (gs[t] == 1) {
-                for (u32 b = 0; b < n; b++) HIP_TRY(launch_centre_ext(c, level, mask, in[b], xs, xl, (c0 + b) * 9 + t, st));
+                if (fused_taps && n_centre == 1) {  // the tap without a rotation rides on the fused launch
+                    centre_mask = mask;
+                    centre_tap = t;
+                } else {
+                    for (u32 b = 0; b < n; b++) HIP_TRY(launch_centre_ext(c, level, mask, in[b], xs, xl, (c0 + b) * 9 + t, st));
+                }
                 continue;
             }
             tkeys[n_taps] = rot_keys[t]->d_key;
@@ -291,7 +297,7 @@ int conv_deferred(const ckks_ctx* c, const he_conv_desc* d, const u32* gs, const
         }
         if (fused_taps) {
             HIP_TRY(launch_key_inner_taps(c, level, ws.digits, ws.dig_b, tkeys, tg, tmasks, ttap, n_taps, in, xs, xl, c0 * 9, 9, n, kscratch,
-                                          c0 == 0, st));  // the masked keys are made once, by the first batch
+                                          c0 == 0, st, centre_mask, centre_tap));  // the masked keys are made once, by the first batch
         } else {  // many digits: one launch per tap (classic layout: every term is a [2][E][N] array)
             for (u32 i = 0; i < n_taps; i++) {
                 u64* outs[CT_BATCH];

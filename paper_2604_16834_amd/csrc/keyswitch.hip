@@ -337,6 +337,8 @@ struct TapSet {
     u32 ginv[8];  // inverse Galois elements: the destination of source point x under sigma_g is gather(x, g^-1)
     u32 tap[8];
     u32 n_taps;
+    const u64* centre_mask;  // the tap without a rotation (P * ct times this mask), or null
+    u32 centre_tap;
 };
 
 // The tap's mask is folded into the key before the batch runs: mk[i][j][comp][e][x] = mask_i[e][x] * key_i[j][comp][t(e)][x]
@@ -352,6 +354,10 @@ __global__ __launch_bounds__(KS_THREADS) void mask_keys_kernel(TapSet T, u64* __
     const u32 e = blockIdx.y, i = blockIdx.z;
     const u32 t = e <= level ? e : num_q + (e - level - 1);
     const ModConst m = mc[t];
+    if (i == T.n_taps) {  // the centre tap has no key: only mask * P
+        if (e <= level) mp[((size_t)i * (level + 1) + e) * N + x] = mulmod_barrett(T.centre_mask[(size_t)e * N + x], m.q - negp[e], m);
+        return;
+    }
     const u64 mv = T.mask[i][(size_t)e * N + x];
     for (u32 j = 0; j < beta; j++)
         for (u32 comp = 0; comp < 2; comp++)
@@ -429,11 +435,24 @@ __global__ __launch_bounds__(KS_THREADS) void key_inner_taps_kernel(const u64* _
             }
         }
     }
+    if (T.centre_mask) {  // no rotation: mask * P * ct on the live limbs, zero on the special primes
+        const u64 kp = has_add ? mp[((size_t)T.n_taps * (level + 1) + e) * N + xsrc] : 0;
+        u64* ot = xs + xl.at(k0base + T.centre_tap, 0, e, xsrc);
+#pragma unroll
+        for (u32 b = 0; b < CT_BATCH; b++) {
+            if (b < n) {
+                const u64 c1 = has_add ? c0s.p[b][((size_t)(level + 1) + e) * N + xsrc] : 0;
+                u64* ob = ot + (size_t)b * k_bstride * xl.s_k;
+                ob[0] = has_add ? mulmod_barrett(cv[b], kp, m) : 0;
+                ob[xl.s_comp] = has_add ? mulmod_barrett(c1, kp, m) : 0;
+            }
+        }
+    }
 }
 
 // words of scratch launch_key_inner_taps needs (the masked keys)
 size_t key_inner_taps_scratch_elems(const ckks_ctx* c, u32 level, u32 n_taps) {
-    return (size_t)n_taps * c->N * ((size_t)c->live_digits(level) * 2 * c->ext_limbs(level) + level + 1);
+    return (size_t)n_taps * c->N * ((size_t)c->live_digits(level) * 2 * c->ext_limbs(level) + level + 1) + (size_t)c->N * (level + 1);
 }
 
 // keys / gs / masks / taps: n_taps <= 8 entries (taps[i] = position of tap i in the output's tap stride);
@@ -442,7 +461,8 @@ size_t key_inner_taps_scratch_elems(const ckks_ctx* c, u32 level, u32 n_taps) {
 // Needs beta <= 4 (returns hipErrorNotSupported otherwise: the caller then falls back to one launch per tap).
 hipError_t launch_key_inner_taps(const ckks_ctx* c, u32 level, const u64* digits, size_t digits_bstride, const u64* const* keys,
                                  const u32* gs, const u64* const* masks, const u32* taps, u32 n_taps, const u64* const* c0s,
-                                 u64* xs, XLayout xl, u32 k0, u32 k_bstride, u32 n, u64* scratch, bool prepare, hipStream_t st) {
+                                 u64* xs, XLayout xl, u32 k0, u32 k_bstride, u32 n, u64* scratch, bool prepare, hipStream_t st,
+                                 const u64* centre_mask, u32 centre_tap) {
     if (n_taps == 0 || n == 0) return hipSuccess;
     if (n_taps > 8 || n > CT_BATCH) return hipErrorInvalidValue;
     const u32 E = c->ext_limbs(level), beta = c->live_digits(level);
@@ -464,6 +484,8 @@ hipError_t launch_key_inner_taps(const ckks_ctx* c, u32 level, const u64* digits
         T.ginv[i] = (u32)inv;
     }
     T.n_taps = n_taps;
+    T.centre_mask = centre_mask;
+    T.centre_tap = centre_tap;
     PtrList8 cl;
     for (u32 b = 0; b < KS_MAX_BATCH; b++) cl.p[b] = b < n ? c0s[b] : nullptr;
     u64* mk = scratch;
@@ -472,7 +494,7 @@ hipError_t launch_key_inner_taps(const ckks_ctx* c, u32 level, const u64* digits
     if (prepare) {
         const u64* negp = c->d_moddown + 2 * c->k_pad + (size_t)c->k_pad * c->num_q + 2 * c->num_q;
         ProfScope ps__(c, K_MASK_MUL, st, 8.0 * c->N * n_taps * (E * (4.0 * beta + 1.0) + level + 1.0), 2.0 * c->N * n_taps * E * beta);
-        hipLaunchKernelGGL(mask_keys_kernel, dim3(nxb, E, n_taps), dim3(KS_THREADS), 0, st, T, mk, mp, negp, c->d_mc, c->N, level, c->num_q,
+        hipLaunchKernelGGL(mask_keys_kernel, dim3(nxb, E, n_taps + (centre_mask ? 1 : 0)), dim3(KS_THREADS), 0, st, T, mk, mp, negp, c->d_mc, c->N, level, c->num_q,
                            c->M, E, beta);
     }
     dim3 grid(nxb, E);
