@@ -87,36 +87,41 @@ def cpu_baseline(wl, params, alignment, act_merged):
     keys = {o: key for o in offs if o}
     q_mac = [q[t] for t in orc.ext_moduli_idx(level)] if deferred else list(q[:level + 1])
     pts = [uniform_residues((len(q_mac), orc.N), q_mac, "cpu_pt%d" % i) for i in range(9)]
+    R_ALIGN, R_MAC, R_OUT, R_ACT = 8, 64, 8, 8              # repetitions: about 15 s of CPU work in all
     t0 = time.perf_counter()
-    if deferred:
-        aligned = orc.align_deferred(ct, level, wl.width, keys)
-    elif alignment == "four_keys":
-        aligned = orc.align_four_keys(ct, level, wl.width, keys)
-    else:
-        aligned = orc.align_direct(ct, level, wl.width, keys)
-    t_align = time.perf_counter() - t0                      # one input channel: its nine aligned copies
-    t0 = time.perf_counter()
-    acc = orc.mac_ext(pts, aligned, level) if deferred else orc.ptct_mac(pts, aligned, level)
-    t_mac = time.perf_counter() - t0                        # 9 taps of one (input, output) channel pair
-    t0 = time.perf_counter()
-    if merged:
-        x = np.stack([orc.moddown_rescale(acc[0], level), orc.moddown_rescale(acc[1], level)])
-    else:
+    for _ in range(R_ALIGN):
         if deferred:
-            acc = np.stack([orc.moddown(acc[0], level), orc.moddown(acc[1], level)])
-        x = orc.rescale(acc, level)
-    t_out = time.perf_counter() - t0                        # one output channel: (ModDown and) rescale
+            aligned = orc.align_deferred(ct, level, wl.width, keys)
+        elif alignment == "four_keys":
+            aligned = orc.align_four_keys(ct, level, wl.width, keys)
+        else:
+            aligned = orc.align_direct(ct, level, wl.width, keys)
+    t_align = (time.perf_counter() - t0) / R_ALIGN          # one input channel: its nine aligned copies
     t0 = time.perf_counter()
-    (orc.poly_activation_merged if act_merged else orc.poly_activation)(x, level - 1, (3 << 40, -(5 << 40), 7 << 40, -(9 << 40)), key)
-    t_act = time.perf_counter() - t0
+    for _ in range(R_MAC):
+        acc = orc.mac_ext(pts, aligned, level) if deferred else orc.ptct_mac(pts, aligned, level)
+    t_mac = (time.perf_counter() - t0) / R_MAC              # 9 taps of one (input, output) channel pair
+    t0 = time.perf_counter()
+    for _ in range(R_OUT):
+        if merged:
+            x = np.stack([orc.moddown_rescale(acc[0], level), orc.moddown_rescale(acc[1], level)])
+        else:
+            u = np.stack([orc.moddown(acc[0], level), orc.moddown(acc[1], level)]) if deferred else acc
+            x = orc.rescale(u, level)
+    t_out = (time.perf_counter() - t0) / R_OUT              # one output channel: (ModDown and) rescale
+    t0 = time.perf_counter()
+    for _ in range(R_ACT):
+        (orc.poly_activation_merged if act_merged else orc.poly_activation)(x, level - 1, (3 << 40, -(5 << 40), 7 << 40, -(9 << 40)), key)
+    t_act = (time.perf_counter() - t0) / R_ACT
     step = wl.c_in * t_align + wl.c_in * wl.c_out * t_mac + wl.c_out * (t_out + t_act)
     cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
     return {
         "value": step * 1e3 / wl.batch, "unit": "ms/image", "cores": cores, "kind": "oracle",
-        "sample": ("oracle (%s schedule) timed on one input channel's alignment (%.2f s), one 9-tap multiply-accumulate "
-                   "(%.2f s), one output channel's %srescale (%.2f s) and one degree-7 activation (%.2f s) at full size, "
-                   "extrapolated to %d alignments, %d 9-tap MACs, %d output channels and activations"
-                   % (alignment, t_align, t_mac, "ModDown + " if deferred else "", t_out, t_act, wl.c_in, wl.c_in * wl.c_out, wl.c_out)),
+        "sample": ("oracle (%s schedule) timed at full size on %d input channels' alignments (%.2f s each), %d 9-tap "
+                   "multiply-accumulates (%.3f s each), %d output channels' %srescale (%.2f s each) and %d degree-7 activations "
+                   "(%.2f s each): %.0f s of CPU work, extrapolated to %d alignments, %d 9-tap MACs, %d output channels and activations"
+                   % (alignment, R_ALIGN, t_align, R_MAC, t_mac, R_OUT, "ModDown + " if deferred else "", t_out, R_ACT, t_act,
+                      R_ALIGN * t_align + R_MAC * t_mac + R_OUT * t_out + R_ACT * t_act, wl.c_in, wl.c_in * wl.c_out, wl.c_out)),
         "step_seconds_extrapolated": step,
     }
 
