@@ -62,6 +62,8 @@ def parse_args():
                          "with the rescale (deferred_merged, the default)")
     ap.add_argument("--two-step-activation", action="store_true",
                     help="activation with separate ModDown and rescale after every product (default: merged into one division)")
+    ap.add_argument("--single-stream", action="store_true",
+                    help="keep all work on one stream for the whole run (channel batches do not overlap): what the profiling runs use")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--no-kernel-timing", action="store_true", help="skip the per-kernel event pass")
     ap.add_argument("--no-microbench", action="store_true", help="skip the rotation and NTT microbenchmarks")
@@ -171,6 +173,8 @@ def main():
                            alignment=mode)
         hx.he_poly_act_deg7(ctx, conv_out, level - 1, k_act, rlk, outs=act_out, ws=ws, merged=act_merged)
 
+    if args.single_stream:
+        hx.ckks_ctx_set_overlap(ctx, False)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -179,6 +183,16 @@ def main():
         step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    # the same K steps with every launch on the caller's stream: the per-kernel timings below are taken that way, because
+    # the duration of a launch that shares the chip with a launch of another batch is not a property of its kernel
+    hx.ckks_ctx_set_overlap(ctx, False)
+    step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_single = (time.perf_counter() - t0) * 1e3 / args.steps
     ms_per_step = elapsed * 1e3 / args.steps
     print("[bench] %d steps, %.2f ms/step" % (args.steps, ms_per_step), file=sys.stderr, flush=True)
 
@@ -194,7 +208,10 @@ def main():
         "config": {"workload": wl.name, "log_n": params.log_n, "limbs": params.num_q, "special_primes": params.num_p,
                    "dnum": params.dnum, "c_in": wl.c_in, "c_out": wl.c_out, "image": "%dx%d" % (wl.height, wl.width),
                    "batch": wl.batch, "rotations_per_step": n_rot, "keyswitches_per_step": n_keyswitch,
-                   "conv_schedule": args.alignment, "activation": "merged_division" if act_merged else "two_step"},
+                   "conv_schedule": args.alignment, "activation": "merged_division" if act_merged else "two_step",
+                   "channel_batches_overlap": not args.single_stream},
+        "ms_per_step_single_stream": ms_single,
+        "kernel_timing": "per-kernel figures and the roofline are measured with all work on one stream (no overlap between channel batches)",
     }
 
     # per-kernel event timing over one more step (every launch bracketed on its own stream)
@@ -263,6 +280,7 @@ def main():
         print(json.dumps(result))
         return
     # ---- the two microbenchmark shapes, reported next to the headline value ------------------------
+    hx.ckks_ctx_set_overlap(ctx, not args.single_stream)
     # rotation microbenchmark (24 limbs + 8 special primes, dnum 3): one ciphertext, 64 distinct offsets, 64 keys in
     # 64 separate 96 MiB buffers (their contents are clones of the eight seeded keys: only the addresses matter)
     n_rot_mb = 64

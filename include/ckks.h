@@ -71,6 +71,14 @@ int ckks_ctx_create(const ckks_params* params, ckks_ctx** out_ctx);
 void ckks_ctx_destroy(ckks_ctx* ctx);
 const char* ckks_last_error_string(const ckks_ctx* ctx);
 
+/* Scheduling (not from the paper).  Operations made of independent channel batches (he_conv_batched in the deferred
+ * schedules, he_poly_act_deg7) run every other batch on a second stream owned by the context, between a fork after the
+ * caller's earlier work and a join before the call's last enqueue on the caller's stream: arithmetic-bound and
+ * traffic-bound kernels of different batches overlap.  The caller still sees one ordered stream.  on = 0 keeps all work
+ * on the caller's stream (per-kernel timings are then not blurred by overlap); default on.  Results are identical.
+ * With overlap on, such calls must not be issued on one context from several host threads at the same time. */
+int ckks_ctx_set_overlap(ckks_ctx* ctx, int on);
+
 typedef enum ckks_op {
     CKKS_OP_KEYSWITCH = 0,
     CKKS_OP_ROTATE = 1,        /* count = number of rotations in the call */

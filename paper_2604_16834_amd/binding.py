@@ -45,7 +45,7 @@ EXPORTS = (
     "ckks_keyswitch", "ckks_rotate_hoisted", "ckks_ptct_mac", "ckks_rescale", "ckks_ctct_mul_relin",
     "he_conv_workspace_bytes", "he_conv_batched", "he_poly_act_deg7",
     "he_accumulator_workspace_bytes", "he_accumulator_merge", "he_fc_workspace_bytes", "he_fc_batched",
-    "he_relayout_workspace_bytes", "he_relayout_two_rotations", "ckks_key_expand_a", "ckks_keyset_stage",
+    "he_relayout_workspace_bytes", "he_relayout_two_rotations", "ckks_key_expand_a", "ckks_keyset_stage", "ckks_ctx_set_overlap",
     "ckks_prof_kernel_count", "ckks_prof_kernel_name", "ckks_prof_begin", "ckks_prof_end",
 )
 
@@ -111,6 +111,7 @@ def _bind(path: str):
     lib.he_relayout_workspace_bytes.restype = sz
     lib.he_relayout_two_rotations.argtypes = [vp, C.POINTER(vp), u32, u32, C.POINTER(C.c_int32), u32, C.POINTER(vp), C.POINTER(C.c_int32),
                                               u32, C.POINTER(vp), C.POINTER(vp), u32, C.POINTER(vp), vp, sz, vp]
+    lib.ckks_ctx_set_overlap.argtypes = [vp, i32]
     lib.ckks_key_expand_a.argtypes = [vp, C.c_uint64, vp, vp]
     lib.ckks_keyset_stage.argtypes = [vp, C.POINTER(vp), C.POINTER(C.c_uint64), C.POINTER(vp), u32, vp]
     lib.ckks_prof_kernel_count.restype = u32
@@ -413,6 +414,11 @@ def he_accumulator_merge(ctx: Context, cts: Sequence[torch.Tensor], level: int, 
     ctx._check(_lib.he_accumulator_merge(ctx.handle, ca, g, level, sts, _ptr(mask), ka, _ptr(out), _ptr(ws),
                                          ws.numel() * ws.element_size(), _stream(stream)))
     return out
+
+
+def ckks_ctx_set_overlap(ctx: Context, on: bool) -> None:
+    """Whether channel batches may run on the context's second stream (default on)."""
+    ctx._check(_lib.ckks_ctx_set_overlap(ctx.handle, 1 if on else 0))
 
 
 def ckks_key_expand_a(ctx: Context, a_seed: int, key: torch.Tensor, stream=None) -> torch.Tensor:

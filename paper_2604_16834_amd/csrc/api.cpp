@@ -28,6 +28,11 @@ int set_err(const ckks_ctx* c, int code, const char* msg) {
     } while (0)
 
 // bump allocator over the caller's workspace (256-byte aligned blocks of u64)
+int set_hip_err(const ckks_ctx* c, hipError_t e) {
+    c->err = std::string("HIP: ") + hipGetErrorString(e);
+    return CKKS_ERR_HIP;
+}
+
 struct Arena {
     char* base;
     size_t cap, used;
@@ -247,26 +252,66 @@ size_t ws_poly_act(const ckks_ctx* c, u32 level, u32 n) {
 // basis Q_level P (inner product + P * sigma_g(c0), times the tap's mask), the sum over (input channel,
 // tap) is taken there, and only the C_out sums go through ModDown and the rescale.  gs: Galois
 // elements of the nine taps (1 = no rotation); masks [9][E][N], w_res [C_out][C_in][9][E].
+// per-lane scratch of the deferred convolution: the key-switch buffers, a batch of un-rescaled outputs, the rescale's scratch
+size_t ws_conv_lane(const ckks_ctx* c, u32 level) {
+    return ws_ks(c, level, CT_BATCH, CT_BATCH) + blk((size_t)CT_BATCH * 2 * (level + 1) * c->N) + ws_rescale(c, level, CT_BATCH);
+}
+u32 conv_lanes(const ckks_ctx* c, const he_conv_desc* d) {  // two batches in flight when there is more than one
+    return (c->side_stream() && (d->c_in > CT_BATCH || d->c_out > CT_BATCH)) ? 2 : 1;
+}
+
 int conv_deferred(const ckks_ctx* c, const he_conv_desc* d, const u32* gs, const uint64_t* const* h_d_in,
                   const ckks_key* const* rot_keys, const u64* masks, const u64* w_res, uint64_t* const* h_d_out, void* d_ws,
-                  size_t ws_bytes, hipStream_t st) {
+                  size_t ws_bytes, hipStream_t st0) {
     const u32 level = d->level, E = c->ext_limbs(level);
     const bool merged = d->alignment == HE_CONV_DEFERRED_MERGED;  // ModDown and rescale of the sums as one division
     const size_t N = c->N, L1 = level + 1, ct_elems = 2 * L1 * N, x_elems = 2 * (size_t)E * N;
     Arena ar(d_ws, ws_bytes);
-    KsWs ws;
-    bool ok = carve_ks(c, level, CT_BATCH, CT_BATCH, ar, ws);
     u64* xs = ar.take((size_t)d->c_in * 9 * x_elems);
     u64* acc = ar.take((size_t)d->c_out * x_elems);
     u64* wscratch = ar.take(weighted_sum_scratch_elems(c, E, d->c_in * 9, d->c_out));
-    u64* tmp = ar.take((size_t)CT_BATCH * ct_elems);
     u64* kscratch = ar.take(key_inner_taps_scratch_elems(c, level, 8));
+    // Batches of input channels (alignment) and of output channels (division) are independent: with room for two sets of
+    // scratch every other batch runs on the library's side stream, between a fork and a join on the caller's stream.
+    const size_t lane_bytes = ws_conv_lane(c, level);
+    const u32 n_lanes = (conv_lanes(c, d) == 2 && ar.ok() && ar.used + 2 * lane_bytes <= ar.cap) ? 2 : 1;
+    struct Lane {
+        KsWs ws;
+        u64* tmp;
+        Arena rest;
+        hipStream_t st;
+    };
+    Lane lanes[2] = {{KsWs{}, nullptr, Arena(nullptr, 0), st0}, {KsWs{}, nullptr, Arena(nullptr, 0), c->side}};
+    bool ok = ar.ok();
+    for (u32 l = 0; l < n_lanes && ok; l++) {
+        ok = carve_ks(c, level, CT_BATCH, CT_BATCH, ar, lanes[l].ws);
+        lanes[l].tmp = ar.take((size_t)CT_BATCH * ct_elems);
+        u64* r = ar.take(ws_rescale(c, level, CT_BATCH) / sizeof(u64));
+        lanes[l].rest = Arena(r, ws_rescale(c, level, CT_BATCH));
+        ok = ok && ar.ok();
+    }
+    if (!ok) return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for the convolution");
     // the aligned copies are stored term-innermost when the fused inner product can write them that way
     const bool fused_taps = c->live_digits(level) <= 4;
     const XLayout xl = (fused_taps && N % 64 == 0) ? XLayout::tiled((size_t)d->c_in * 9, N) : XLayout::classic(E, N);
-    if (!ok || !ar.ok() || ar.used + ws_rescale(c, level, CT_BATCH) > ar.cap)
-        return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for the convolution");
-    for (u32 c0 = 0; c0 < d->c_in; c0 += CT_BATCH) {
+    bool forked = false;
+    auto fork = [&]() -> int {
+        if (n_lanes < 2 || forked) return CKKS_OK;
+        HIP_TRY(hipEventRecord(c->ev_fork, st0));
+        HIP_TRY(hipStreamWaitEvent(c->side, c->ev_fork, 0));
+        forked = true;
+        return CKKS_OK;
+    };
+    auto join = [&](int rc) -> int {  // also on the error paths: the caller's stream never runs ahead of the side stream
+        if (!forked) return rc;
+        forked = false;
+        hipError_t e = hipEventRecord(c->ev_join, c->side);
+        if (e == hipSuccess) e = hipStreamWaitEvent(st0, c->ev_join, 0);
+        return (e != hipSuccess && rc == CKKS_OK) ? set_hip_err(c, e) : rc;
+    };
+    auto align_batch = [&](u32 c0, const Lane& L) -> int {
+        const KsWs& ws = L.ws;
+        hipStream_t st = L.st;
         const u32 n = d->c_in - c0 < CT_BATCH ? d->c_in - c0 : CT_BATCH;
         const u64 *in[CT_BATCH], *c1s[CT_BATCH];
         for (u32 b = 0; b < n; b++) {
@@ -305,26 +350,35 @@ int conv_deferred(const ckks_ctx* c, const he_conv_desc* d, const u32* gs, const
                 HIP_TRY(launch_key_inner_ext(c, level, ws.digits, ws.dig_b, tkeys[i], tg[i], in, nullptr, tmasks[i], outs, n, st));
             }
         }
+        return CKKS_OK;
+    };
+    int rc;
+    for (u32 c0 = 0, k = 0; c0 < d->c_in; c0 += CT_BATCH, k++) {
+        // the first batch also prepares the masked keys on the caller's stream; the fork comes after it
+        if ((rc = align_batch(c0, lanes[k == 0 ? 0 : (n_lanes == 2 ? k & 1 : 0)]))) return join(rc);
+        if (k == 0 && c0 + CT_BATCH < d->c_in && (rc = fork())) return rc;
     }
-    HIP_TRY(launch_weighted_sum(c, level, true, xs, xl, d->c_in * 9, w_res, d->c_out, acc, wscratch, st));
-    for (u32 o0 = 0; o0 < d->c_out; o0 += CT_BATCH) {
+    if ((rc = join(CKKS_OK))) return rc;
+    HIP_TRY(launch_weighted_sum(c, level, true, xs, xl, d->c_in * 9, w_res, d->c_out, acc, wscratch, st0));
+    if (d->c_out > CT_BATCH && (rc = fork())) return rc;
+    for (u32 o0 = 0, k = 0; o0 < d->c_out; o0 += CT_BATCH, k++) {
+        const Lane& L = lanes[forked ? k & 1 : 0];
         const u32 n = d->c_out - o0 < CT_BATCH ? d->c_out - o0 : CT_BATCH;
-        KsWs wd = ws;
+        KsWs wd = L.ws;
         wd.v = acc + (size_t)o0 * x_elems;  // the sums take the place of a batch of inner products
         wd.v_b = x_elems;
         FinalItem items[CT_BATCH];
         const u64* ins[CT_BATCH];
         u64* outs[CT_BATCH];
         for (u32 b = 0; b < n; b++) {
-            ins[b] = tmp + (size_t)b * ct_elems;
+            ins[b] = L.tmp + (size_t)b * ct_elems;
             outs[b] = (u64*)h_d_out[o0 + b];
-            items[b] = FinalItem{nullptr, nullptr, nullptr, merged ? outs[b] : tmp + (size_t)b * ct_elems, 1, 0};
+            items[b] = FinalItem{nullptr, nullptr, nullptr, merged ? outs[b] : L.tmp + (size_t)b * ct_elems, 1, 0};
         }
-        int rc = run_moddown(c, level, wd, n, items, st, merged);
-        if (rc) return rc;
-        if (!merged && (rc = run_rescale(c, level, ins, L1 * N, outs, n, ar.rest(), st))) return rc;
+        if ((rc = run_moddown(c, level, wd, n, items, L.st, merged))) return join(rc);
+        if (!merged && (rc = run_rescale(c, level, ins, L1 * N, outs, n, L.rest, L.st))) return join(rc);
     }
-    return CKKS_OK;
+    return join(CKKS_OK);
 }
 
 // n <= CT_BATCH different ciphertexts srcs[b] ([2][level+1][N]) rotated, outs[b] = Rot(srcs[b]) with keys[b] / gal[b]
@@ -624,7 +678,8 @@ size_t ckks_workspace_bytes(const ckks_ctx* c, int op, uint32_t level, uint32_t 
         case CKKS_OP_ROTATE: return c->dnum ? ws_ks(c, level, 1, nb) + blk(L1 * N) : 0;
         case CKKS_OP_RESCALE: return level >= 1 ? ws_rescale(c, level, 1) : 0;
         case CKKS_OP_CTCT_MUL_RELIN: return c->dnum ? ws_ctct(c, level, 1) : 0;
-        case CKKS_OP_POLY_ACT: return (c->dnum && level >= 4) ? ws_poly_act(c, level, nb) : 0;
+        // more than one batch of channels: two batches in flight (one on the library's side stream), each with its own scratch
+        case CKKS_OP_POLY_ACT: return (c->dnum && level >= 4) ? ws_poly_act(c, level, nb) * (count > CT_BATCH && c->side ? 2 : 1) : 0;  // sized for overlap on
         default: return 0;
     }
 }
@@ -634,13 +689,19 @@ size_t he_conv_workspace_bytes(const ckks_ctx* c, const he_conv_desc* d) {
     const size_t N = c->N, L1 = d->level + 1;
     if (d->alignment == HE_CONV_DEFERRED_MODDOWN || d->alignment == HE_CONV_DEFERRED_MERGED) {
         const size_t E = c->ext_limbs(d->level);
-        return ws_ks(c, d->level, CT_BATCH, CT_BATCH) + blk((size_t)d->c_in * 9 * 2 * E * N) + blk((size_t)d->c_out * 2 * E * N) +
-               blk(weighted_sum_scratch_elems(c, (u32)E, d->c_in * 9, d->c_out)) + blk((size_t)CT_BATCH * 2 * L1 * N) +
-               blk(key_inner_taps_scratch_elems(c, d->level, 8)) + ws_rescale(c, d->level, CT_BATCH);
+        const u32 lanes = (c->side && (d->c_in > CT_BATCH || d->c_out > CT_BATCH)) ? 2 : 1;  // sized for overlap on
+        return lanes * ws_conv_lane(c, d->level) + blk((size_t)d->c_in * 9 * 2 * E * N) + blk((size_t)d->c_out * 2 * E * N) +
+               blk(weighted_sum_scratch_elems(c, (u32)E, d->c_in * 9, d->c_out)) + blk(key_inner_taps_scratch_elems(c, d->level, 8));
     }
     return ws_ks(c, d->level, CT_BATCH, CT_BATCH) + blk((size_t)d->c_in * 9 * 2 * L1 * N) + blk((size_t)d->c_out * 2 * L1 * N) +
            blk(weighted_sum_scratch_elems(c, (u32)L1, d->c_in * 9, d->c_out)) + ws_rescale(c, d->level, CT_BATCH) +
            (d->alignment == HE_CONV_ALIGN_FOUR_KEYS ? 2 * blk((size_t)CT_BATCH * 2 * L1 * N) : 0);
+}
+
+int ckks_ctx_set_overlap(ckks_ctx* c, int on) {
+    if (!c) return CKKS_ERR_INVALID_ARG;
+    c->overlap = on != 0;
+    return CKKS_OK;
 }
 
 uint32_t ckks_galois_element(const ckks_ctx* c, int32_t offset) {
@@ -1183,15 +1244,12 @@ int he_poly_act_deg7(const ckks_ctx* c, const uint64_t* const* h_d_x, uint32_t n
     const u32 l1 = level - 1, l2 = level - 2, l3 = level - 3;
     const size_t xs = (size_t)(level + 1) * N;  // component stride of x
     const size_t x2s = (size_t)(l1 + 1) * N, x3s = (size_t)(l2 + 1) * N, Bs = (size_t)(l3 + 1) * N;
-    Arena ar(d_ws, ws_bytes);
-    u64* x2 = ar.take(nb_max * 2 * x2s);        // level-1
-    u64* x3 = ar.take(nb_max * 2 * x3s);        // level-2
-    u64* x4 = ar.take(nb_max * 2 * x3s);        // level-2
-    u64* B = ar.take(nb_max * 2 * Bs);          // level-3
-    u64* tmp = ar.take(nb_max * 2 * xs);        // un-rescaled products
-    if (!ar.ok() || ar.used + ws_ctct(c, level, nb_max) + ws_rescale(c, level, nb_max) > ar.cap)
-        return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for the activation");
-    hipStream_t st = (hipStream_t)stream;
+    // Batches of channels are independent: with room for two sets of scratch, every other batch goes to the library's side
+    // stream (fork after the caller's earlier work, join before the call returns to the caller's stream).
+    const size_t lane_bytes = ws_poly_act(c, level, nb_max);
+    const u32 n_lanes = (n_ct > CT_BATCH && c->side_stream() && ws_bytes >= 2 * lane_bytes) ? 2 : 1;
+    if (ws_bytes < lane_bytes || !d_ws) return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for the activation");
+    hipStream_t st0 = (hipStream_t)stream;
     auto residues = [&](int64_t k, u32 lv, u64* out) {
         for (u32 i = 0; i <= lv; i++) {
             const u64 q = c->mod[i];
@@ -1199,9 +1257,33 @@ int he_poly_act_deg7(const ckks_ctx* c, const uint64_t* const* h_d_x, uint32_t n
         }
     };
     u64 ka[CKKS_MAX_MODULI], kb[CKKS_MAX_MODULI];
+    if (n_lanes == 2) {
+        HIP_TRY(hipEventRecord(c->ev_fork, st0));
+        HIP_TRY(hipStreamWaitEvent(c->side, c->ev_fork, 0));
+    }
+    auto join = [&](int rc) -> int {  // also on the error paths: the caller's stream never runs ahead of the side stream
+        if (n_lanes == 2) {
+            hipError_t e = hipEventRecord(c->ev_join, c->side);
+            if (e == hipSuccess) e = hipStreamWaitEvent(st0, c->ev_join, 0);
+            if (e != hipSuccess && rc == CKKS_OK) {
+                c->err = std::string("joining the side stream: ") + hipGetErrorString(e);
+                return CKKS_ERR_HIP;
+            }
+        }
+        return rc;
+    };
 
-    for (u32 i0 = 0; i0 < n_ct; i0 += CT_BATCH) {
+    for (u32 i0 = 0, batch_no = 0; i0 < n_ct; i0 += CT_BATCH, batch_no++) {
         const u32 n = n_ct - i0 < CT_BATCH ? n_ct - i0 : CT_BATCH;
+        const u32 lane = n_lanes == 2 ? (batch_no & 1) : 0;
+        hipStream_t st = lane ? c->side : st0;
+        Arena ar((char*)d_ws + (size_t)lane * lane_bytes, lane_bytes);
+        u64* x2 = ar.take(nb_max * 2 * x2s);        // level-1
+        u64* x3 = ar.take(nb_max * 2 * x3s);        // level-2
+        u64* x4 = ar.take(nb_max * 2 * x3s);        // level-2
+        u64* B = ar.take(nb_max * 2 * Bs);          // level-3
+        u64* tmp = ar.take(nb_max * 2 * xs);        // un-rescaled products
+        if (!ar.ok()) return join(set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for the activation"));
         // pointer lists of this batch: inputs, and the per-item slices of the intermediates
         const u64 *px[CT_BATCH], *px2[CT_BATCH], *px3[CT_BATCH], *px4[CT_BATCH], *pB[CT_BATCH], *ptmp[CT_BATCH];
         u64 *ox2[CT_BATCH], *ox3[CT_BATCH], *ox4[CT_BATCH], *oB[CT_BATCH], *otmp[CT_BATCH], *oout[CT_BATCH];
@@ -1218,49 +1300,49 @@ int he_poly_act_deg7(const ckks_ctx* c, const uint64_t* const* h_d_x, uint32_t n
         };
         int rc;
         if (merged_division) {  // every relinearise-then-rescale pair as one division by P*q_level
-            if ((rc = run_ctct_merged(c, level, px, xs, px, xs, nullptr, 0, rlk->d_key, ox2, n, ar.rest(), st))) return rc;
-            if ((rc = run_ctct_merged(c, l1, px2, x2s, px, xs, nullptr, 0, rlk->d_key, ox3, n, ar.rest(), st))) return rc;
-            if ((rc = run_ctct_merged(c, l1, px2, x2s, px2, x2s, nullptr, 0, rlk->d_key, ox4, n, ar.rest(), st))) return rc;
+            if ((rc = run_ctct_merged(c, level, px, xs, px, xs, nullptr, 0, rlk->d_key, ox2, n, ar.rest(), st))) return join(rc);
+            if ((rc = run_ctct_merged(c, l1, px2, x2s, px, xs, nullptr, 0, rlk->d_key, ox3, n, ar.rest(), st))) return join(rc);
+            if ((rc = run_ctct_merged(c, l1, px2, x2s, px2, x2s, nullptr, 0, rlk->d_key, ox4, n, ar.rest(), st))) return join(rc);
             residues(h_k[2], l2, ka);
             residues(h_k[3], l2, kb);
             tmp_at(x3s);
-            HIP_TRY(launch_lincomb2(c, l2, ptr_list(px, n), xs, ka, ptr_list(px3, n), x3s, kb, nullptr, 0, tmp, 2 * x3s, n, st));
-            if ((rc = run_rescale(c, l2, ptmp, x3s, oB, n, ar.rest(), st))) return rc;
+            if (hipError_t he_ = (launch_lincomb2(c, l2, ptr_list(px, n), xs, ka, ptr_list(px3, n), x3s, kb, nullptr, 0, tmp, 2 * x3s, n, st)); he_ != hipSuccess) return join(set_hip_err(c, he_));
+            if ((rc = run_rescale(c, l2, ptmp, x3s, oB, n, ar.rest(), st))) return join(rc);
             // y = Rescale(x4 * B + (k1 * x + k3 * x3)): the linear part rides along as the product's addend
             residues(h_k[0], l3, ka);
             residues(h_k[1], l3, kb);
-            HIP_TRY(launch_lincomb2(c, l3, ptr_list(px, n), xs, ka, ptr_list(px3, n), x3s, kb, nullptr, 0, tmp, 2 * Bs, n, st));
-            if ((rc = run_ctct_merged(c, l3, px4, x3s, pB, Bs, tmp, 2 * Bs, rlk->d_key, oout, n, ar.rest(), st))) return rc;
+            if (hipError_t he_ = (launch_lincomb2(c, l3, ptr_list(px, n), xs, ka, ptr_list(px3, n), x3s, kb, nullptr, 0, tmp, 2 * Bs, n, st)); he_ != hipSuccess) return join(set_hip_err(c, he_));
+            if ((rc = run_ctct_merged(c, l3, px4, x3s, pB, Bs, tmp, 2 * Bs, rlk->d_key, oout, n, ar.rest(), st))) return join(rc);
             continue;
         }
         // x2 = Rescale(x * x)                                  level -> level-1
         tmp_at(xs);
-        if ((rc = run_ctct(c, level, px, xs, px, xs, rlk->d_key, otmp, n, ar.rest(), st))) return rc;
-        if ((rc = run_rescale(c, level, ptmp, xs, ox2, n, ar.rest(), st))) return rc;
+        if ((rc = run_ctct(c, level, px, xs, px, xs, rlk->d_key, otmp, n, ar.rest(), st))) return join(rc);
+        if ((rc = run_rescale(c, level, ptmp, xs, ox2, n, ar.rest(), st))) return join(rc);
         // x3 = Rescale(x2 * x), x4 = Rescale(x2 * x2)           level-1 -> level-2
         tmp_at(x2s);
-        if ((rc = run_ctct(c, l1, px2, x2s, px, xs, rlk->d_key, otmp, n, ar.rest(), st))) return rc;
-        if ((rc = run_rescale(c, l1, ptmp, x2s, ox3, n, ar.rest(), st))) return rc;
-        if ((rc = run_ctct(c, l1, px2, x2s, px2, x2s, rlk->d_key, otmp, n, ar.rest(), st))) return rc;
-        if ((rc = run_rescale(c, l1, ptmp, x2s, ox4, n, ar.rest(), st))) return rc;
+        if ((rc = run_ctct(c, l1, px2, x2s, px, xs, rlk->d_key, otmp, n, ar.rest(), st))) return join(rc);
+        if ((rc = run_rescale(c, l1, ptmp, x2s, ox3, n, ar.rest(), st))) return join(rc);
+        if ((rc = run_ctct(c, l1, px2, x2s, px2, x2s, rlk->d_key, otmp, n, ar.rest(), st))) return join(rc);
+        if ((rc = run_rescale(c, l1, ptmp, x2s, ox4, n, ar.rest(), st))) return join(rc);
         // B = Rescale(k5 * x + k7 * x3)                         level-2 -> level-3
         residues(h_k[2], l2, ka);
         residues(h_k[3], l2, kb);
         tmp_at(x3s);
-        HIP_TRY(launch_lincomb2(c, l2, ptr_list(px, n), xs, ka, ptr_list(px3, n), x3s, kb, nullptr, 0, tmp, 2 * x3s, n, st));
-        if ((rc = run_rescale(c, l2, ptmp, x3s, oB, n, ar.rest(), st))) return rc;
+        if (hipError_t he_ = (launch_lincomb2(c, l2, ptr_list(px, n), xs, ka, ptr_list(px3, n), x3s, kb, nullptr, 0, tmp, 2 * x3s, n, st)); he_ != hipSuccess) return join(set_hip_err(c, he_));
+        if ((rc = run_rescale(c, l2, ptmp, x3s, oB, n, ar.rest(), st))) return join(rc);
         // y = Rescale((k1 * x + k3 * x3) + x4 * B)              level-3 -> level-4
         u64* prod = x2;  // x2 is no longer needed; n * [2][l3+1][N] fits in it
         u64* oprod[CT_BATCH];
         for (u32 b = 0; b < n; b++) oprod[b] = prod + b * 2 * Bs;
-        if ((rc = run_ctct(c, l3, px4, x3s, pB, Bs, rlk->d_key, oprod, n, ar.rest(), st))) return rc;
+        if ((rc = run_ctct(c, l3, px4, x3s, pB, Bs, rlk->d_key, oprod, n, ar.rest(), st))) return join(rc);
         residues(h_k[0], l3, ka);
         residues(h_k[1], l3, kb);
         tmp_at(Bs);
-        HIP_TRY(launch_lincomb2(c, l3, ptr_list(px, n), xs, ka, ptr_list(px3, n), x3s, kb, prod, 2 * Bs, tmp, 2 * Bs, n, st));
-        if ((rc = run_rescale(c, l3, ptmp, Bs, oout, n, ar.rest(), st))) return rc;
+        if (hipError_t he_ = (launch_lincomb2(c, l3, ptr_list(px, n), xs, ka, ptr_list(px3, n), x3s, kb, prod, 2 * Bs, tmp, 2 * Bs, n, st)); he_ != hipSuccess) return join(set_hip_err(c, he_));
+        if ((rc = run_rescale(c, l3, ptmp, Bs, oout, n, ar.rest(), st))) return join(rc);
     }
-    return CKKS_OK;
+    return join(CKKS_OK);
 }
 
 // ---- optional per-kernel timing -------------------------------------------------------------------

@@ -70,6 +70,9 @@ extern "C" void ckks_ctx_destroy(ckks_ctx* c) {
     (void)hipFree(c->d_moddown);
     (void)hipFree(c->d_moddown_rs);
     (void)hipFree(c->d_rescale);
+    if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
+    if (c->ev_join) (void)hipEventDestroy(c->ev_join);
+    if (c->side) (void)hipStreamDestroy(c->side);
     delete c;
 }
 
@@ -293,6 +296,15 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
         g_create_error = std::string("HIP error while building tables: ") + hipGetErrorString(e);
         ckks_ctx_destroy(c);
         return CKKS_ERR_HIP;
+    }
+    // the side stream is an optimisation: without it everything runs on the caller's stream
+    if (hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking) != hipSuccess) c->side = nullptr;
+    if (c->side && (hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming) != hipSuccess ||
+                    hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming) != hipSuccess)) {
+        if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
+        (void)hipStreamDestroy(c->side);
+        c->side = nullptr;
+        c->ev_fork = c->ev_join = nullptr;
     }
     *out = c;
     return CKKS_OK;

@@ -125,6 +125,15 @@ struct ckks_ctx {
                                       // ModDown and rescale as one division by P*q_l; see moddown_rs_table()
     u64* d_rescale = nullptr;         // [num_q][num_q][3]: (q_l^-1 mod q_i, its Shoup companion, q_l mod q_i)
 
+    // A second stream of the library's own (default priority) with the two events of a fork/join: operations made of
+    // independent channel batches put every other batch on it, so that kernels bound by arithmetic overlap with
+    // kernels bound by memory traffic.  The caller sees all work ordered in its own stream.  Calls that use it must
+    // not be issued on one context from several host threads at once.
+    hipStream_t side = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    bool overlap = true;  // ckks_ctx_set_overlap: off = everything on the caller's stream
+    hipStream_t side_stream() const { return overlap ? side : nullptr; }
+
     mutable std::string err;
     mutable ProfState* prof = nullptr;  // non-null between ckks_prof_begin and ckks_prof_end
 

@@ -381,6 +381,36 @@ def test_fc_batched_rejects_bad_shapes_and_keys():
     assert e.value.code == hx.binding.CKKS_ERR_WORKSPACE_TOO_SMALL
 
 
+def test_overlap_switch_gives_identical_results():
+    """Twenty channels (three batches, two of them in flight at a time on the context's two streams) through the
+    activation with the overlap on and off, repeatedly into the same outputs: every result equals the oracle's."""
+    wl = CONFIGS["small_block"]
+    p = wl.params()
+    orc, ctx = both(p)
+    level = p.num_q - 1
+    s, s_ntt = orc.gen_secret(901)
+    rlk = orc.gen_relin_key(s_ntt, 902)
+    d_rlk = hx.ckks_key_load(ctx, hx.from_host(rlk), 0)
+    rng = np.random.default_rng(903)
+    plan = orc.act_schedule(level, 2.0 ** 50)
+    cts = [orc.encrypt(rng.uniform(-1, 1, orc.n), 2.0 ** 50, level, s_ntt, 904 + i) for i in range(20)]
+    want = [orc.poly_activation_merged(ct, level, plan["k"], rlk) for ct in cts[:3]] + [None] * 17
+    want[8], want[19] = (orc.poly_activation_merged(cts[i], level, plan["k"], rlk) for i in (8, 19))
+    dx = [hx.from_host(ct) for ct in cts]
+    outs = None
+    for on in (True, False, True, True):
+        hx.ckks_ctx_set_overlap(ctx, on)
+        outs = hx.he_poly_act_deg7(ctx, dx, level, plan["k"], d_rlk, outs=outs, merged=True)
+        got = [hx.to_host(o) for o in outs]
+        for i, w in enumerate(want):
+            if w is not None:
+                assert np.array_equal(got[i], w), f"overlap {on}, channel {i}"
+        if on is False:
+            ref = got
+    for a, b in zip(got, ref):
+        assert np.array_equal(a, b)
+
+
 # --------------------------------------------------------------------------------- staged keys
 @pytest.mark.parametrize("log_n,num_q,num_p,dnum,bits", [(12, 4, 2, 2, 50), (10, 3, 1, 3, 57), (5, 3, 1, 2, 12)])
 def test_key_expansion_matches_oracle(log_n, num_q, num_p, dnum, bits):
