@@ -6,17 +6,21 @@
  * primitives underneath them, which the paper uses through a library (Background: "Rotations and
  * Key Switching", "RNS Decomposition and NTT Optimization"; Experiments, "HE Security Parameters":
  * digit-decomposed key switching, rescaling), plus the ciphertext product that the polynomial
- * activation needs ("Other Layers").  The server side only: key generation, encryption and
- * decryption belong to the client (Threat Model) and are not part of this library.
+ * activation needs ("Other Layers"), the batched fully connected layer ("Fully Connected Layer"), and
+ * the pipeline's accumulator, down-sampling compaction and key staging ("Optimized Inference
+ * Pipeline").  The server side only: key generation, encryption and decryption belong to the client
+ * (Threat Model) and are not part of this library.
  *
  * Conventions shared by every call
  *   - Every function returns CKKS_OK (0) or a negative ckks_status; nothing throws or aborts.
  *     ckks_last_error_string() gives the reason of the last failure on that context.
  *   - Pointers named d_* are DEVICE pointers owned by the caller; pointers named h_* and all
  *     structs are HOST memory.  Hot calls never allocate, free or synchronise: work is enqueued on
- *     the caller's stream (a hipStream_t passed as void*, NULL = default stream) and scratch space
- *     comes from the caller's workspace (d_ws, ws_bytes; size from ckks_workspace_bytes()).  The
- *     caller keeps every buffer alive until the stream has drained.
+ *     the caller's stream (a hipStream_t passed as void*, NULL = default stream; two calls may put
+ *     part of it on a second stream of the context's, joined before they return: see
+ *     ckks_ctx_set_overlap) and scratch space comes from the caller's workspace (d_ws, ws_bytes; size
+ *     from the *_workspace_bytes() queries).  The caller keeps every buffer alive until the stream
+ *     has drained.
  *   - A polynomial limb is N uint64 residues in [0, q) (canonical on input and on output).
  *     Polynomials are in evaluation (NTT) form: entry k of a limb is the value at
  *     psi^(2*bitrev(k)+1), psi the 2N-th root given for that modulus.  ckks_ntt_fwd maps
@@ -49,7 +53,7 @@ typedef enum ckks_status {
     CKKS_ERR_HIP = -6                 /* a HIP runtime call failed */
 } ckks_status;
 
-typedef struct ckks_ctx ckks_ctx; /* immutable after creation; may be shared by concurrent calls */
+typedef struct ckks_ctx ckks_ctx; /* tables immutable after creation; see ckks_ctx_set_overlap for calls from several threads */
 typedef struct ckks_key ckks_key;
 
 /* Parameter set.  Supported: 4 <= log_n <= 17; num_q >= 1; num_q + num_p <= 64; every modulus a
@@ -65,8 +69,9 @@ typedef struct ckks_params {
 } ckks_params;
 
 /* Builds the context on the current HIP device: twiddle tables, reduction constants, basis-
- * conversion tables for every level.  This is the only call that allocates device memory
- * (about 32*N bytes per modulus) and it synchronises the device once. */
+ * conversion tables for every level, plus a stream and two events (ckks_ctx_set_overlap).  This is the
+ * only call that allocates device memory (about 32*N bytes per modulus) and it synchronises the
+ * device once. */
 int ckks_ctx_create(const ckks_params* params, ckks_ctx** out_ctx);
 void ckks_ctx_destroy(ckks_ctx* ctx);
 const char* ckks_last_error_string(const ckks_ctx* ctx);
