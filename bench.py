@@ -64,6 +64,8 @@ def parse_args():
                     help="activation with separate ModDown and rescale after every product (default: merged into one division)")
     ap.add_argument("--single-stream", action="store_true",
                     help="keep all work on one stream for the whole run (channel batches do not overlap): what the profiling runs use")
+    ap.add_argument("--wide-weights", action="store_true",
+                    help="do not state the bound on the integer weights (the multiply-accumulate then takes them as full residues)")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--no-kernel-timing", action="store_true", help="skip the per-kernel event pass")
     ap.add_argument("--no-microbench", action="store_true", help="skip the rotation and NTT microbenchmarks")
@@ -158,7 +160,14 @@ def main():
     # operands of the multiply-accumulate live on the extended basis (q_0..q_level, p_0..) in the deferred schedule
     q_mac = (q[:level + 1] + q[params.num_q:]) if deferred else q[:level + 1]
     masks = hx.from_host(uniform_residues((9, len(q_mac), N), q_mac, "masks"))
-    w_res = hx.from_host(uniform_residues((wl.c_out * wl.c_in * 9, len(q_mac), 1), q_mac, "w").reshape(wl.c_out, wl.c_in, 9, len(q_mac)))
+    # integer weights as the layer has them: N(0, 2 / (9 C_in)) kernels times the weight scale q_level 2^10 / 2^28 (the
+    # convolution's output then lands at scale 2^50), rounded: 31-bit integers, given by their residues
+    import numpy as np
+    from workloads import conv_weights
+    w_real = conv_weights(wl.c_out, wl.c_in, dist="he_normal").reshape(wl.c_out, wl.c_in, 9)
+    w_int = np.where(w_real >= 0, np.floor(w_real * (q[level] * 2.0 ** 10 / 2.0 ** 28) + 0.5), np.ceil(w_real * (q[level] * 2.0 ** 10 / 2.0 ** 28) - 0.5)).astype(np.int64)
+    weight_bits = 0 if args.wide_weights else hx.conv_weight_bits(w_int)
+    w_res = hx.from_host(np.stack([np.mod(w_int, qi).astype(np.uint64) for qi in q_mac], axis=-1))
     conv_out = [hx.empty(2, level, N) for _ in range(wl.c_out)]
     act_out = [hx.empty(2, level - 4, N) for _ in range(wl.c_out)]
     k_act = (3 << 40, -(5 << 40), 7 << 40, -(9 << 40))
@@ -170,7 +179,7 @@ def main():
 
     def step():
         hx.he_conv_batched(ctx, wl.height, wl.width, wl.batch, level, ins, keys, masks, w_res, wl.c_out, outs=conv_out, ws=ws,
-                           alignment=mode)
+                           alignment=mode, weight_bits=weight_bits)
         hx.he_poly_act_deg7(ctx, conv_out, level - 1, k_act, rlk, outs=act_out, ws=ws, merged=act_merged)
 
     if args.single_stream:
@@ -209,7 +218,7 @@ def main():
                    "dnum": params.dnum, "c_in": wl.c_in, "c_out": wl.c_out, "image": "%dx%d" % (wl.height, wl.width),
                    "batch": wl.batch, "rotations_per_step": n_rot, "keyswitches_per_step": n_keyswitch,
                    "conv_schedule": args.alignment, "activation": "merged_division" if act_merged else "two_step",
-                   "channel_batches_overlap": not args.single_stream},
+                   "channel_batches_overlap": not args.single_stream, "weight_bits": weight_bits},
         "ms_per_step_single_stream": ms_single,
         "kernel_timing": "per-kernel figures and the roofline are measured with all work on one stream (no overlap between channel batches)",
     }

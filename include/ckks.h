@@ -200,6 +200,11 @@ typedef enum he_conv_alignment {
 typedef struct he_conv_desc {
     uint32_t c_in, c_out, height, width, batch, level;
     uint32_t alignment; /* he_conv_alignment; all give the same slots up to noise, different residues */
+    uint32_t weight_bits; /* 0, or a promise that every weight is an integer w with |w| < 2^(weight_bits-1) (d_w_res
+                             holds w mod each modulus): weights are a real number times the weight scale, rounded, so
+                             they are far narrower than a residue, and the multiply-accumulate then writes them in 3
+                             (weight_bits <= 24) or 4 (<= 32) signed 8-bit digits instead of 7.  Same residues out;
+                             a weight beyond the promised bound gives wrong residues without an error. */
 } he_conv_desc;
 
 /* Workspace bytes he_conv_batched needs for this shape (0 on invalid arguments): the shared

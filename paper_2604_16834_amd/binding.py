@@ -65,7 +65,7 @@ class _Params(C.Structure):
 
 class _ConvDesc(C.Structure):
     _fields_ = [("c_in", C.c_uint32), ("c_out", C.c_uint32), ("height", C.c_uint32), ("width", C.c_uint32),
-                ("batch", C.c_uint32), ("level", C.c_uint32), ("alignment", C.c_uint32)]
+                ("batch", C.c_uint32), ("level", C.c_uint32), ("alignment", C.c_uint32), ("weight_bits", C.c_uint32)]
 
 
 class _FcDesc(C.Structure):
@@ -324,15 +324,23 @@ def ckks_ctct_mul_relin(ctx: Context, a: torch.Tensor, b: torch.Tensor, level: i
 
 def he_conv_workspace_bytes(ctx: Context, c_in: int, c_out: int, height: int, width: int, batch: int, level: int,
                             alignment: int = HE_CONV_ALIGN_DIRECT) -> int:
-    d = _ConvDesc(c_in, c_out, height, width, batch, level, int(alignment))
+    d = _ConvDesc(c_in, c_out, height, width, batch, level, int(alignment), 0)
     return int(_lib.he_conv_workspace_bytes(ctx.handle, C.byref(d)))
+
+
+def conv_weight_bits(w_int) -> int:
+    """The smallest weight_bits that holds for these integer weights (host array): |w| < 2^(bits-1)."""
+    import numpy as np
+    m = int(np.abs(np.asarray(w_int, dtype=np.int64)).max()) if np.size(w_int) else 0
+    return m.bit_length() + 1
 
 
 def he_conv_batched(ctx: Context, height: int, width: int, batch: int, level: int, ins: Sequence[torch.Tensor],
                     rot_keys: Sequence[Optional[Key]], tap_masks: torch.Tensor, w_res: torch.Tensor, c_out: int,
                     outs: Optional[List[torch.Tensor]] = None, ws: Optional[torch.Tensor] = None, stream=None,
-                    alignment: int = HE_CONV_ALIGN_DIRECT) -> List[torch.Tensor]:
-    """alignment: HE_CONV_ALIGN_DIRECT (eight hoisted rotations), HE_CONV_ALIGN_FOUR_KEYS (the paper's two-stage
+                    alignment: int = HE_CONV_ALIGN_DIRECT, weight_bits: int = 0) -> List[torch.Tensor]:
+    """weight_bits: 0, or the promise |w| < 2^(weight_bits-1) for every integer weight (see conv_weight_bits).
+    alignment: HE_CONV_ALIGN_DIRECT (eight hoisted rotations), HE_CONV_ALIGN_FOUR_KEYS (the paper's two-stage
     alignment with four keys), HE_CONV_DEFERRED_MODDOWN (one division by P per output channel) or
     HE_CONV_DEFERRED_MERGED (that division merged with the rescale).
     ins: C_in tensors [2][level+1][N]; rot_keys: nine entries in tap order (centre ignored);
@@ -353,7 +361,7 @@ def he_conv_batched(ctx: Context, height: int, width: int, batch: int, level: in
     for o in outs:
         if o.numel() != 2 * level * ctx.N:
             raise ValueError("each output must be [2][level][N]")
-    d = _ConvDesc(c_in, c_out, height, width, batch, level, int(alignment))
+    d = _ConvDesc(c_in, c_out, height, width, batch, level, int(alignment), int(weight_bits))
     ws = _ws(ctx, ws, he_conv_workspace_bytes(ctx, c_in, c_out, height, width, batch, level, alignment))
     ia = _ptr_array([_ptr(t) for t in ins])
     ka = _ptr_array([k.handle.value if k is not None else None for k in rot_keys])

@@ -359,7 +359,7 @@ int conv_deferred(const ckks_ctx* c, const he_conv_desc* d, const u32* gs, const
         if (k == 0 && c0 + CT_BATCH < d->c_in && (rc = fork())) return rc;
     }
     if ((rc = join(CKKS_OK))) return rc;
-    HIP_TRY(launch_weighted_sum(c, level, true, xs, xl, d->c_in * 9, w_res, d->c_out, acc, wscratch, st0));
+    HIP_TRY(launch_weighted_sum(c, level, true, xs, xl, d->c_in * 9, w_res, d->c_out, acc, wscratch, d->weight_bits, st0));
     if (d->c_out > CT_BATCH && (rc = fork())) return rc;
     for (u32 o0 = 0, k = 0; o0 < d->c_out; o0 += CT_BATCH, k++) {
         const Lane& L = lanes[forked ? k & 1 : 0];
@@ -1033,7 +1033,7 @@ int he_conv_batched(const ckks_ctx* c, const he_conv_desc* d, const uint64_t* co
         }
     }
     // convolution evaluation: integer-weighted sum over (input channel, tap) for every output channel
-    HIP_TRY(launch_weighted_sum(c, level, false, xs, XLayout::classic(L1, N), d->c_in * 9, (const u64*)d_w_res, d->c_out, acc, wscratch, st));
+    HIP_TRY(launch_weighted_sum(c, level, false, xs, XLayout::classic(L1, N), d->c_in * 9, (const u64*)d_w_res, d->c_out, acc, wscratch, d->weight_bits, st));
     for (u32 o0 = 0; o0 < d->c_out; o0 += CT_BATCH) {
         const u32 n = d->c_out - o0 < CT_BATCH ? d->c_out - o0 : CT_BATCH;
         const u64* ins[CT_BATCH];

@@ -225,13 +225,14 @@ hipError_t launch_add_plain(const ckks_ctx* c, u32 level, const u64* pt, u64* ct
 hipError_t launch_ct_sum(const ckks_ctx* c, u32 level, const PtrList8& items, u32 n, u64* out, hipStream_t st, bool extended = false);
 hipError_t launch_centre_ext(const ckks_ctx* c, u32 level, const u64* mask, const u64* ct, u64* xs, XLayout xl, u32 k, hipStream_t st);
 size_t weighted_sum_scratch_elems(const ckks_ctx* c, u32 n_limbs, u32 n_terms, u32 c_out);
+// weight_bits: the caller's bound |w| < 2^(weight_bits - 1) on the integers behind w_res (0 = none)
 hipError_t launch_weighted_sum(const ckks_ctx* c, u32 level, bool extended, const u64* xs, XLayout xl, u32 n_terms, const u64* w_res,
-                               u32 c_out, u64* acc, u64* scratch, hipStream_t st);
+                               u32 c_out, u64* acc, u64* scratch, u32 weight_bits, hipStream_t st);
 // wsum_mfma.hip
 bool wsum_mfma_applies(const ckks_ctx* c, u32 n_terms);
 size_t wsum_mfma_scratch_elems(u32 n_limbs, u32 n_terms, u32 c_out);
 hipError_t launch_wsum_mfma(const ckks_ctx* c, u32 level, u32 nl, const u64* xs, XLayout xl, u32 n_terms, const u64* w_res, u32 c_out,
-                            u64* acc, u64* scratch, hipStream_t st);
+                            u64* acc, u64* scratch, u32 weight_bits, hipStream_t st);
 hipError_t launch_lincomb2(const ckks_ctx* c, u32 level, const PtrList8& a, size_t a_cstride, const u64* ka, const PtrList8& b,
                            size_t b_cstride, const u64* kb, const u64* add, size_t add_bstride, u64* out, size_t out_bstride, u32 n,
                            hipStream_t st);

@@ -341,12 +341,12 @@ size_t weighted_sum_scratch_elems(const ckks_ctx* c, u32 n_limbs, u32 n_terms, u
 // with `extended`, level+1+num_p (the extended basis: positions above `level` are the special primes).
 // scratch: weighted_sum_scratch_elems() words (may be null when that is 0)
 hipError_t launch_weighted_sum(const ckks_ctx* c, u32 level, bool extended, const u64* xs, XLayout xl, u32 n_terms, const u64* w_res,
-                               u32 c_out, u64* acc, u64* scratch, hipStream_t st) {
+                               u32 c_out, u64* acc, u64* scratch, u32 weight_bits, hipStream_t st) {
     const u32 L1 = extended ? c->ext_limbs(level) : level + 1;
     const double bytes = 16.0 * c->N * L1 * ((double)n_terms + c_out), ops = 2.0 * c->N * L1 * n_terms * c_out;
     if (wsum_mfma_applies(c, n_terms)) {  // moduli below 2^50: exact 8-bit digit products on the matrix cores
         ProfScope ps__(c, K_WEIGHTED_SUM, st, bytes, ops);
-        return launch_wsum_mfma(c, level, L1, xs, xl, n_terms, w_res, c_out, acc, scratch, st);
+        return launch_wsum_mfma(c, level, L1, xs, xl, n_terms, w_res, c_out, acc, scratch, weight_bits, st);
     }
     dim3 grid((c->N + PW_THREADS - 1) / PW_THREADS, 2 * L1, (c_out + WS_OUT_TILE - 1) / WS_OUT_TILE);
     ProfScope ps__(c, K_WEIGHTED_SUM, st, bytes, ops);

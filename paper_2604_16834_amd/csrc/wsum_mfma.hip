@@ -19,18 +19,21 @@
 // into digits and transposes bytes in registers (v_perm_b32) into the B operands.  The digit planes
 // of the weights are prepared once per call in the A-operand lane layout and staged through LDS
 // (double-buffered) so that the waves share them.  X streams from HBM exactly once.
+//
+// The weights are small integers (a real weight times the weight scale, rounded), not arbitrary residues: when the
+// caller states a bound |w| < 2^(bits-1), the centred representative of each weight residue is written in DW = 3 (24
+// bits) or 4 (32 bits) signed digits instead of 7, which leaves 7*DW digit products (21 or 28 instead of 49) and
+// 7+DW-1 diagonals.  Same exact integer sum, same canonical residues.
 #include "ctx.h"
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 
 #define WM_THREADS 256
-#define WM_DIGITS 7
-#define WM_DIAGS (2 * WM_DIGITS - 1)
+#define WM_DIGITS 7                                     // digits of an X value
 #define WM_BIAS 0x0080808080808080ull
 #define WM_OT_PER_WG 2                                  // output tiles of 32 channels per workgroup
-#define WM_A_STAGE (WM_OT_PER_WG * WM_DIGITS * 2 * 64)  // uint4 words of one 64-term block of weights (28 KiB)
-#define WM_A_PER_THREAD (WM_A_STAGE / WM_THREADS)       // 7
+#define WM_B_STAGE (WM_OT_PER_WG * WM_DIGITS * 2 * 64)  // uint4 words of one 64-term block of X digits (28 KiB)
 
 // bytes 0..6 = the seven signed base-256 digits of v < 2^55 (two's complement bytes)
 __host__ __device__ __forceinline__ u64 signed_digits(u64 v) { return (v + WM_BIAS) ^ WM_BIAS; }
@@ -39,20 +42,23 @@ __host__ __device__ __forceinline__ u64 signed_digits(u64 v) { return (v + WM_BI
 // wa[(((e*KB + kb)*OT + ot)*7 + dw)*2 + ks][lane] = 16 bytes: digit dw of
 //   W[32*ot + lane%32][64*kb + 32*ks + 16*(lane/32) + j], j < 16
 // (zero beyond c_out / n_terms; OT = number of 32-channel tiles rounded up to a multiple of 2)
-__global__ __launch_bounds__(WM_THREADS) void wsum_prep_kernel(const u64* __restrict__ w_res, uint4* __restrict__ wa, u32 c_out,
-                                                               u32 n_terms, u32 nl, u32 KB, u32 OT) {
+// DW < 7: the weights are centred first (v > q/2 -> v - q), DW digits hold them when |w| < 2^(8 DW - 1)
+__global__ __launch_bounds__(WM_THREADS) void wsum_prep_kernel(const u64* __restrict__ w_res, uint4* __restrict__ wa,
+                                                               const ModConst* __restrict__ mc, u32 level, u32 num_q, u32 c_out,
+                                                               u32 n_terms, u32 nl, u32 KB, u32 OT, u32 DW) {
     const size_t idx = (size_t)blockIdx.x * WM_THREADS + threadIdx.x;
-    if (idx >= (size_t)nl * KB * OT * WM_DIGITS * 2 * 64) return;
+    if (idx >= (size_t)nl * KB * OT * DW * 2 * 64) return;
     const u32 lane = (u32)(idx & 63);
     size_t r = idx >> 6;
     const u32 ks = (u32)(r & 1);
     r >>= 1;
-    const u32 dw = (u32)(r % WM_DIGITS);
-    r /= WM_DIGITS;
+    const u32 dw = (u32)(r % DW);
+    r /= DW;
     const u32 ot = (u32)(r % OT);
     r /= OT;
     const u32 kb = (u32)(r % KB), e = (u32)(r / KB);
     const u32 o = 32 * ot + (lane & 31), k0 = 64 * kb + 32 * ks + 16 * (lane >> 5);
+    const u64 q = mc[e <= level ? e : num_q + (e - level - 1)].q;
     u32 words[4];
 #pragma unroll
     for (u32 m = 0; m < 4; m++) {
@@ -60,7 +66,8 @@ __global__ __launch_bounds__(WM_THREADS) void wsum_prep_kernel(const u64* __rest
 #pragma unroll
         for (u32 j = 0; j < 4; j++) {
             const u32 k = k0 + 4 * m + j;
-            const u64 v = (o < c_out && k < n_terms) ? w_res[((size_t)o * n_terms + k) * nl + e] : 0;
+            u64 v = (o < c_out && k < n_terms) ? w_res[((size_t)o * n_terms + k) * nl + e] : 0;
+            if (DW < WM_DIGITS && v > (q >> 1)) v -= q;  // two's complement of the negative representative
             wv |= (u32)((signed_digits(v) >> (8 * dw)) & 0xffu) << (8 * j);
         }
         words[m] = wv;
@@ -106,13 +113,17 @@ __device__ __forceinline__ void digits_to_b(const u64* v, uint4* bw) {
 // block kb+1 (requested an iteration ago), request X of block kb+2 and the weights of block kb+2,
 // then run the 98 matrix instructions of block kb out of LDS while the vector ALU turns X of block
 // kb+1 (requested an iteration ago) into digits for the other LDS buffer.
-template <bool RAGGED>
+template <int DW, bool RAGGED>
 __global__ __launch_bounds__(WM_THREADS) void wsum_mfma_kernel(const u64* __restrict__ xs, XLayout xl, const uint4* __restrict__ wa,
                                                                u64* __restrict__ acc, const ModConst* __restrict__ mc,
                                                                const u32* __restrict__ pow256, u32 N, u32 level, u32 nl, u32 num_q,
                                                                u32 n_terms, u32 c_out, u32 KB, u32 OT) {
-    __shared__ uint4 lds_a[2][WM_A_STAGE];
-    __shared__ uint4 lds_b[2][WM_A_STAGE];  // [column tile 2][32-term step 2][digit 7][lane 64]
+    constexpr int DIAGS = WM_DIGITS + DW - 1;
+    constexpr int A_STAGE = WM_OT_PER_WG * DW * 2 * 64;  // uint4 words of one 64-term block of weight digits
+    // vector instructions of the digit conversion issued per matrix instruction (about 200 per block in all)
+    constexpr int VALU_PER_MFMA = (2 * WM_DIGITS * 2 * WM_DIGITS + DW * 2 * WM_DIGITS - 1) / (DW * 2 * WM_DIGITS);
+    __shared__ uint4 lds_a[2][A_STAGE];
+    __shared__ uint4 lds_b[2][WM_B_STAGE];  // [column tile 2][32-term step 2][digit 7][lane 64]
     const u32 tid = threadIdx.x, lane = tid & 63;
     const u32 wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const u32 g = lane >> 5;                 // which 16 terms of a 32-term step this lane holds
@@ -125,9 +136,9 @@ __global__ __launch_bounds__(WM_THREADS) void wsum_mfma_kernel(const u64* __rest
     const size_t off = ((size_t)comp * nl + e) * N + x;
     const bool x_ok = !RAGGED || x < N;
 
-    v16i d[WM_DIAGS];
+    v16i d[DIAGS];
 #pragma unroll
-    for (int s = 0; s < WM_DIAGS; s++)
+    for (int s = 0; s < DIAGS; s++)
 #pragma unroll
         for (int r = 0; r < 16; r++) d[s][r] = 0;
 
@@ -135,8 +146,8 @@ __global__ __launch_bounds__(WM_THREADS) void wsum_mfma_kernel(const u64* __rest
     const u32 xc = x_ok ? x : N - 1;
     const u64* xbase = xs + comp * xl.s_comp + e * xl.s_e + (size_t)(32 * wt) * xl.s_k;
     const u32 lane_off = (u32)(16 * g * xl.s_k + (size_t)(xc >> 6) * xl.s_xt + (xc & 63));
-    const uint4* wsrc = wa + ((size_t)e * KB * OT + ot0) * (WM_DIGITS * 2 * 64) + tid;  // block kb: + kb * wstep
-    const size_t wstep = (size_t)OT * (WM_DIGITS * 2 * 64);
+    const uint4* wsrc = wa + ((size_t)e * KB * OT + ot0) * (DW * 2 * 64) + tid;  // block kb: + kb * wstep
+    const size_t wstep = (size_t)OT * (DW * 2 * 64);
     u64 raw0[16], raw1[16];
     uint4 ap0, ap1, ap2, ap3, ap4, ap5, ap6;  // named, not an array: they live across the loop's back edge in registers
 #define WM_LOAD_X(RAW, KBLK)                                                                          \
@@ -153,10 +164,18 @@ __global__ __launch_bounds__(WM_THREADS) void wsum_mfma_kernel(const u64* __rest
         _Pragma("unroll") for (u32 j = 0; j < 16; j++)                                                \
             RAW[j] &= (x_ok && 64 * (KBLK) + 32 * wt + 16 * g + j < n_terms) ? ~0ull : 0ull;          \
     }
-#define WM_A_EACH(OP) \
-    { OP(0, ap0) OP(1, ap1) OP(2, ap2) OP(3, ap3) OP(4, ap4) OP(5, ap5) OP(6, ap6) }
-#define WM_A_LD(I, V) V = wsrc[kblk__ * wstep + I * WM_THREADS];
-#define WM_A_ST(I, V) lds_a[buf__][tid + I * WM_THREADS] = V;
+#define WM_A_EACH(OP)                                                                                \
+    {                                                                                                 \
+        if (DW > 0) OP(0, ap0)                                                                        \
+        if (DW > 1) OP(1, ap1)                                                                        \
+        if (DW > 2) OP(2, ap2)                                                                        \
+        if (DW > 3) OP(3, ap3)                                                                        \
+        if (DW > 4) OP(4, ap4)                                                                        \
+        if (DW > 5) OP(5, ap5)                                                                        \
+        if (DW > 6) OP(6, ap6)                                                                        \
+    }
+#define WM_A_LD(I, V) { V = wsrc[kblk__ * wstep + I * WM_THREADS]; }
+#define WM_A_ST(I, V) { lds_a[buf__][tid + I * WM_THREADS] = V; }
 #define WM_LOAD_A(KBLK) { const size_t kblk__ = (KBLK); WM_A_EACH(WM_A_LD) }
 #define WM_STORE_A(BUF) { const u32 buf__ = (BUF); WM_A_EACH(WM_A_ST) }
 #define WM_STORE_B(RAW, BUF)                                                                          \
@@ -175,7 +194,7 @@ __global__ __launch_bounds__(WM_THREADS) void wsum_mfma_kernel(const u64* __rest
         WM_LOAD_X(RAW_NEW, kx)                                                                        \
         WM_LOAD_A(kx)                                                                                 \
         __builtin_amdgcn_sched_barrier(0);                                                            \
-        const uint4* la = &lds_a[cur][wt * (WM_DIGITS * 2 * 64) + lane];                              \
+        const uint4* la = &lds_a[cur][wt * (DW * 2 * 64) + lane];                                     \
         const uint4* lb = &lds_b[cur][xt * (2 * WM_DIGITS * 64) + lane];                              \
         v4i b[WM_DIGITS][2];                                                                          \
         _Pragma("unroll") for (u32 ks = 0; ks < 2; ks++)                                              \
@@ -184,10 +203,10 @@ __global__ __launch_bounds__(WM_THREADS) void wsum_mfma_kernel(const u64* __rest
                 b[dx][ks] = (v4i){(int)t.x, (int)t.y, (int)t.z, (int)t.w};                            \
             }                                                                                         \
         uint4 av = la[0];                                                                             \
-        _Pragma("unroll") for (u32 i = 0; i < WM_DIGITS * 2; i++) {                                   \
+        _Pragma("unroll") for (u32 i = 0; i < DW * 2; i++) {                                          \
             const u32 dw = i >> 1, ks = i & 1;                                                        \
             const v4i a = (v4i){(int)av.x, (int)av.y, (int)av.z, (int)av.w};                          \
-            if (i + 1 < WM_DIGITS * 2) av = la[(i + 1) * 64];                                         \
+            if (i + 1 < DW * 2) av = la[(i + 1) * 64];                                                \
             _Pragma("unroll") for (u32 dx = 0; dx < WM_DIGITS; dx++)                                  \
                 d[dx + dw] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[dx][ks], d[dx + dw], 0, 0, 0); \
         }                                                                                             \
@@ -196,10 +215,10 @@ __global__ __launch_bounds__(WM_THREADS) void wsum_mfma_kernel(const u64* __rest
         /* issue order: the 16 LDS reads that start the block, then per matrix instruction two vector */ \
         /* instructions of the digit conversion, an LDS read every seven, the LDS writes last */        \
         __builtin_amdgcn_sched_group_barrier(0x100, 16, 0);                                           \
-        _Pragma("unroll") for (u32 i = 0; i < WM_DIGITS * 2; i++) {                                   \
+        _Pragma("unroll") for (u32 i = 0; i < DW * 2; i++) {                                          \
             _Pragma("unroll") for (u32 q = 0; q < WM_DIGITS; q++) {                                   \
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                    \
-                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);                                    \
+                __builtin_amdgcn_sched_group_barrier(0x002, VALU_PER_MFMA, 0);                        \
             }                                                                                         \
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                        \
         }                                                                                             \
@@ -237,9 +256,9 @@ __global__ __launch_bounds__(WM_THREADS) void wsum_mfma_kernel(const u64* __rest
     const u32 mi = e <= level ? e : num_q + (e - level - 1);
     const ModConst m = mc[mi];
     const u32* __restrict__ pw = pow256 + (size_t)mi * 26;
-    u32 clo[WM_DIAGS], chi[WM_DIAGS];
+    u32 clo[DIAGS], chi[DIAGS];
 #pragma unroll
-    for (u32 s = 0; s < WM_DIAGS; s++) {
+    for (u32 s = 0; s < DIAGS; s++) {
         clo[s] = pw[2 * s];
         chi[s] = pw[2 * s + 1];
     }
@@ -249,7 +268,7 @@ __global__ __launch_bounds__(WM_THREADS) void wsum_mfma_kernel(const u64* __rest
         if (o >= c_out) continue;
         long long slo = 0, shi = 0;
 #pragma unroll
-        for (u32 s = 0; s < WM_DIAGS; s++) {
+        for (u32 s = 0; s < DIAGS; s++) {
             slo += (long long)d[s][r] * (long long)(int)clo[s];
             shi += (long long)d[s][r] * (long long)(int)chi[s];
         }
@@ -266,26 +285,37 @@ __global__ __launch_bounds__(WM_THREADS) void wsum_mfma_kernel(const u64* __rest
 
 bool wsum_mfma_applies(const ckks_ctx* c, u32 n_terms) { return c->small_q && n_terms <= c->lazy_terms && n_terms <= 4096; }
 
-// scratch words (u64) for the weight digit planes
+// digits the weights are written in, from the caller's bound |w| < 2^(weight_bits - 1) (0 = none: any residue)
+static u32 weight_digits(u32 weight_bits) { return weight_bits == 0 || weight_bits > 32 ? WM_DIGITS : (weight_bits <= 24 ? 3 : 4); }
+
+// scratch words (u64) for the weight digit planes (sized for the widest weights)
 size_t wsum_mfma_scratch_elems(u32 n_limbs, u32 n_terms, u32 c_out) {
     const size_t KB = (n_terms + 63) / 64, OT = (c_out + 63) / 64 * WM_OT_PER_WG;
     return (size_t)n_limbs * KB * OT * WM_DIGITS * 2 * 64 * 2;  // 16 bytes per lane
 }
 
+template <int DW>
+static void launch_wsum_dw(bool ragged, dim3 grid, hipStream_t st, const u64* xs, XLayout xl, const uint4* wa, u64* acc, const ckks_ctx* c,
+                           u32 level, u32 nl, u32 n_terms, u32 c_out, u32 KB, u32 OT) {
+    if (ragged)
+        hipLaunchKernelGGL((wsum_mfma_kernel<DW, true>), grid, dim3(WM_THREADS), 0, st, xs, xl, wa, acc, c->d_mc, c->d_pow256, c->N, level, nl,
+                           c->num_q, n_terms, c_out, KB, OT);
+    else
+        hipLaunchKernelGGL((wsum_mfma_kernel<DW, false>), grid, dim3(WM_THREADS), 0, st, xs, xl, wa, acc, c->d_mc, c->d_pow256, c->N, level, nl,
+                           c->num_q, n_terms, c_out, KB, OT);
+}
+
 hipError_t launch_wsum_mfma(const ckks_ctx* c, u32 level, u32 nl, const u64* xs, XLayout xl, u32 n_terms, const u64* w_res, u32 c_out,
-                            u64* acc, u64* scratch, hipStream_t st) {
-    const u32 KB = (n_terms + 63) / 64, OT = (c_out + 63) / 64 * WM_OT_PER_WG;
-    const size_t prep = (size_t)nl * KB * OT * WM_DIGITS * 2 * 64;
+                            u64* acc, u64* scratch, u32 weight_bits, hipStream_t st) {
+    const u32 KB = (n_terms + 63) / 64, OT = (c_out + 63) / 64 * WM_OT_PER_WG, DW = weight_digits(weight_bits);
+    const size_t prep = (size_t)nl * KB * OT * DW * 2 * 64;
     hipLaunchKernelGGL(wsum_prep_kernel, dim3((u32)((prep + WM_THREADS - 1) / WM_THREADS)), dim3(WM_THREADS), 0, st, w_res,
-                       (uint4*)scratch, c_out, n_terms, nl, KB, OT);
+                       (uint4*)scratch, c->d_mc, level, c->num_q, c_out, n_terms, nl, KB, OT, DW);
     dim3 grid((c->N + 63) / 64, 2 * nl, OT / WM_OT_PER_WG);
     // the 32-bit lane offset of the regular kernel spans 16 terms: 16 * (2 * nl * N) words must fit
     const bool ragged = (n_terms & 63) || (c->N & 63) || 16 * xl.s_k + (size_t)(c->N >> 6) * xl.s_xt + 64 > 0xffffffffull;
-    if (ragged)
-        hipLaunchKernelGGL(wsum_mfma_kernel<true>, grid, dim3(WM_THREADS), 0, st, xs, xl, (const uint4*)scratch, acc, c->d_mc, c->d_pow256, c->N,
-                           level, nl, c->num_q, n_terms, c_out, KB, OT);
-    else
-        hipLaunchKernelGGL(wsum_mfma_kernel<false>, grid, dim3(WM_THREADS), 0, st, xs, xl, (const uint4*)scratch, acc, c->d_mc, c->d_pow256, c->N,
-                           level, nl, c->num_q, n_terms, c_out, KB, OT);
+    if (DW == 3) launch_wsum_dw<3>(ragged, grid, st, xs, xl, (const uint4*)scratch, acc, c, level, nl, n_terms, c_out, KB, OT);
+    else if (DW == 4) launch_wsum_dw<4>(ragged, grid, st, xs, xl, (const uint4*)scratch, acc, c, level, nl, n_terms, c_out, KB, OT);
+    else launch_wsum_dw<WM_DIGITS>(ragged, grid, st, xs, xl, (const uint4*)scratch, acc, c, level, nl, n_terms, c_out, KB, OT);
     return hipGetLastError();
 }

@@ -3,6 +3,7 @@ Where the CPU oracle can afford it the comparison is limb for limb; elsewhere sa
 compared limb for limb and the rest is checked through properties that hold at any size (round
 trips, hoisted == unhoisted, decryption against float64 references)."""
 import numpy as np
+import torch
 import pytest
 
 pytestmark = pytest.mark.gpu
@@ -124,9 +125,16 @@ def test_cfg5_resnet20_stage3_block_slice():
     d_masks = hx.from_host(masks)
     d_masks_ext = hx.from_host(masks_ext)
     d_cts = [hx.from_host(c) for c in cts]
-    conv = hx.he_conv_batched(ctx, wl.height, wl.width, wl.batch, level, d_cts, dkeys, d_masks_ext,
-                              hx.from_host(w_residues(w_int, ext_moduli, len(ext_moduli) - 1)), wl.c_out,
-                              alignment=hx.HE_CONV_DEFERRED_MERGED)
+    wb = hx.conv_weight_bits(w_int)                        # weights scaled by ~2^32: four signed digits
+    assert 24 < wb <= 32
+    d_w = hx.from_host(w_residues(w_int, ext_moduli, len(ext_moduli) - 1))
+    conv = hx.he_conv_batched(ctx, wl.height, wl.width, wl.batch, level, d_cts, dkeys, d_masks_ext, d_w, wl.c_out,
+                              alignment=hx.HE_CONV_DEFERRED_MERGED, weight_bits=wb)
+    wide = hx.he_conv_batched(ctx, wl.height, wl.width, wl.batch, level, d_cts, dkeys, d_masks_ext, d_w, wl.c_out,
+                              alignment=hx.HE_CONV_DEFERRED_MERGED)               # no bound stated: seven digits
+    for o in range(wl.c_out):
+        assert torch.equal(conv[o], wide[o]), f"output channel {o}: four-digit and seven-digit weights disagree"
+    del wide
     scale = 2.0 ** 50
     plan = orc.act_schedule(level - 1, scale)
     d_rlk = hx.ckks_key_load(ctx, hx.from_host(rlk), 0)
@@ -159,7 +167,8 @@ def test_cfg5_resnet20_stage3_block_slice():
     # inputs coincide is not expected (other input channels): compare with the oracle only
     for mode, merged in ((hx.HE_CONV_DEFERRED_MODDOWN, False), (hx.HE_CONV_DEFERRED_MERGED, True)):
         got = hx.he_conv_batched(ctx, wl.height, wl.width, wl.batch, level, [d_cts[c] for c in sub_in], dkeys, d_masks_ext,
-                                 hx.from_host(w_residues(w_sub, ext_moduli, len(ext_moduli) - 1)), len(sub_out), alignment=mode)
+                                 hx.from_host(w_residues(w_sub, ext_moduli, len(ext_moduli) - 1)), len(sub_out), alignment=mode,
+                                 weight_bits=wb if merged else 0)
         want = orc.he_conv_deferred([cts[c] for c in sub_in], level, wl.width, keys, masks_ext, w_sub, merged=merged)
         for i in range(len(sub_out)):
             assert np.array_equal(hx.to_host(got[i]), want[i]), f"deferred slice output {i} (merged division: {merged})"

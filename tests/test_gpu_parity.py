@@ -133,7 +133,7 @@ def test_ctct_mul_relin_matches_oracle(ks_setup, level):
 
 
 # ----------------------------------------------------------------------------------- convolution
-def conv_case(name, level=None, bits=50, four_keys=False, deferred=False, merged=False):
+def conv_case(name, level=None, bits=50, four_keys=False, deferred=False, merged=False, narrow=False):
     wl = CONFIGS[name]
     p = make_params(wl.log_n, wl.num_q, wl.num_p, wl.dnum, bits=bits)
     orc, ctx = both(p)
@@ -154,9 +154,11 @@ def conv_case(name, level=None, bits=50, four_keys=False, deferred=False, merged
     if four_keys:                                 # only the keys of -1, +1, -W, +W exist
         keys = {off: k for off, k in keys.items() if off in (-1, 1, -wl.width, wl.width)}
     dkeys = [hx.ckks_key_load(ctx, hx.from_host(keys[off]), hx.ckks_galois_element(ctx, off)) if off in keys else None for off in offs]
+    wb = hx.conv_weight_bits(w_int) if narrow else 0         # the bound on the integer weights, stated or not
+    assert not narrow or wb <= 24
     outs = hx.he_conv_batched(ctx, wl.height, wl.width, wl.batch, level, [hx.from_host(c) for c in cts], dkeys,
                               hx.from_host(masks), hx.from_host(w_residues(w_int, w_moduli, len(w_moduli) - 1 if deferred else level)),
-                              wl.c_out, alignment=mode)
+                              wl.c_out, alignment=mode, weight_bits=wb)
     return wl, p, orc, level, s_ntt, img, w, scale, cts, keys, masks, w_int, [hx.to_host(o) for o in outs]
 
 
@@ -173,6 +175,19 @@ def test_he_conv_matches_oracle_and_float_conv(name, level, bits):
             continue    # one special prime for 2-limb digits / 36-bit primes under a 2^40 scale: limb parity only
         dec = orc.unpack_channel(orc.decrypt(outs[o], level - 1, s_ntt, scale), wl.batch, wl.height, wl.width)
         assert np.abs(dec - ref[:, o]).max() < 1e-4
+
+
+@pytest.mark.parametrize("name,deferred,merged", [("cfg1_single_conv", False, False), ("small_conv", False, False),
+                                                  ("small_conv", True, False), ("small_conv", True, True)])
+def test_he_conv_with_stated_weight_bound_matches_oracle(name, deferred, merged):
+    """The weights are integers of at most 23 bits: with that bound stated the multiply-accumulate writes them in
+    three signed digits instead of seven (negative ones through their centred representative): same residues."""
+    wl, p, orc, level, s_ntt, img, w, scale, cts, keys, masks, w_int, outs = conv_case(name, deferred=deferred, merged=merged, narrow=True)
+    assert (w_int < 0).any() and (w_int > 0).any()
+    want = orc.he_conv_deferred(cts, level, wl.width, keys, masks, w_int, merged=merged) if deferred \
+        else orc.he_conv(cts, level, wl.width, keys, masks, w_int)
+    for o in range(wl.c_out):
+        assert np.array_equal(outs[o], want[o]), f"output channel {o}"
 
 
 @pytest.mark.parametrize("name,level,bits", [("cfg1_single_conv", None, 50), ("small_conv", None, 50), ("small_conv", 3, 56)])
