@@ -675,7 +675,10 @@ size_t ckks_workspace_bytes(const ckks_ctx* c, int op, uint32_t level, uint32_t 
     const u32 nb = count < 1 ? 1 : (count > CT_BATCH ? CT_BATCH : count);
     switch (op) {
         case CKKS_OP_KEYSWITCH: return c->dnum ? ws_ks(c, level, 1, 1) : 0;
-        case CKKS_OP_ROTATE: return c->dnum ? ws_ks(c, level, 1, nb) + blk(L1 * N) : 0;
+        case CKKS_OP_ROTATE:  // more than one batch: a second set of inner-product and conversion buffers (two batches in flight)
+            return c->dnum ? ws_ks(c, level, 1, nb) + blk(L1 * N) +
+                                 (count > CT_BATCH && c->side ? blk((size_t)nb * 2 * c->ext_limbs(level) * N) + blk((size_t)nb * 2 * L1 * N) : 0)
+                           : 0;
         case CKKS_OP_RESCALE: return level >= 1 ? ws_rescale(c, level, 1) : 0;
         case CKKS_OP_CTCT_MUL_RELIN: return c->dnum ? ws_ctct(c, level, 1) : 0;
         // more than one batch of channels: two batches in flight (one on the library's side stream), each with its own scratch
@@ -836,6 +839,16 @@ int ckks_rotate_hoisted(const ckks_ctx* c, const uint64_t* d_ct, uint32_t level,
         }
     }
     hipStream_t st = (hipStream_t)stream;
+    // More than one batch of hoisted rotations: with room for a second set of inner-product and conversion buffers, every
+    // other batch runs on the context's second stream (its traffic-bound inner products next to the other batch's ModDown).
+    KsWs lane_ws[2] = {ws, ws};
+    bool two_lanes = false;
+    if (hoisted && n_keyed > rb && c->side_stream()) {
+        Arena extra = ar;
+        lane_ws[1].v = extra.take(rb * ws.v_b);
+        lane_ws[1].w = extra.take(rb * ws.w_b);
+        two_lanes = extra.ok();
+    }
     const u64* ct = (const u64*)d_ct;
     const u64* c0 = ct;
     const u64* c1 = ct + L1 * N;
@@ -843,23 +856,37 @@ int ckks_rotate_hoisted(const ckks_ctx* c, const uint64_t* d_ct, uint32_t level,
         int rc = run_modup(c, level, &c1, 1, ws, st);
         if (rc) return rc;
     }
+    if (two_lanes) {
+        HIP_TRY(hipEventRecord(c->ev_fork, st));
+        HIP_TRY(hipStreamWaitEvent(c->side, c->ev_fork, 0));
+    }
+    auto join = [&](int rc) -> int {  // also on the error paths
+        if (!two_lanes) return rc;
+        hipError_t e = hipEventRecord(c->ev_join, c->side);
+        if (e == hipSuccess) e = hipStreamWaitEvent(st, c->ev_join, 0);
+        return (e != hipSuccess && rc == CKKS_OK) ? set_hip_err(c, e) : rc;
+    };
     FinalItem items[CT_BATCH];
-    u32 nb = 0;
+    u32 nb = 0, lane = 0;
     for (u32 t = 0; t < n_rot; t++) {
         const u32 g = ckks_galois_element(c, h_offsets[t]);
         u64* out = (u64*)h_d_outs[t];
         if (g == 1) {
-            HIP_TRY(launch_copy(ct, out, 2 * L1 * N, st));
+            if (hipError_t e = launch_copy(ct, out, 2 * L1 * N, st); e != hipSuccess) return join(set_hip_err(c, e));
             continue;
         }
         if (hoisted) {
             // same digits, one key per rotation; the digits are read through sigma_g
-            HIP_TRY(launch_key_inner(c, level, ws.digits, keys[t]->d_key, g, ws.v + nb * ws.v_b, st));
+            const KsWs& lw = lane_ws[lane];
+            hipStream_t ls = lane ? c->side : st;
+            if (hipError_t e = launch_key_inner(c, level, lw.digits, keys[t]->d_key, g, lw.v + nb * lw.v_b, ls); e != hipSuccess)
+                return join(set_hip_err(c, e));
             items[nb] = FinalItem{c0, nullptr, nullptr, out, g, 0};
             if (++nb == rb) {
-                int rc = run_moddown(c, level, ws, nb, items, st);
-                if (rc) return rc;
+                int rc = run_moddown(c, level, lw, nb, items, ls);
+                if (rc) return join(rc);
                 nb = 0;
+                if (two_lanes) lane ^= 1;
             }
         } else {
             HIP_TRY(launch_automorph(c, (u32)L1, c1, g, pc1, st));
@@ -873,10 +900,10 @@ int ckks_rotate_hoisted(const ckks_ctx* c, const uint64_t* d_ct, uint32_t level,
         }
     }
     if (nb) {
-        int rc = run_moddown(c, level, ws, nb, items, st);
-        if (rc) return rc;
+        int rc = run_moddown(c, level, lane_ws[lane], nb, items, lane ? c->side : st);
+        if (rc) return join(rc);
     }
-    return CKKS_OK;
+    return join(CKKS_OK);
 }
 
 int ckks_ptct_mac(const ckks_ctx* c, const uint64_t* const* h_d_pts, const uint64_t* const* h_d_cts, uint32_t n_terms,
