@@ -426,6 +426,43 @@ def test_overlap_switch_gives_identical_results():
         assert np.array_equal(a, b)
 
 
+def test_two_stream_activation_replays_from_a_graph():
+    """The activation of 20 channels (both of the context's streams in use) captured into a HIP graph: every replay,
+    with eager work and a synchronisation in between, gives the eager (oracle-checked) result."""
+    import torch
+    wl = CONFIGS["small_block"]
+    p = wl.params()
+    orc, ctx = both(p)
+    level = p.num_q - 1
+    s, s_ntt = orc.gen_secret(911)
+    rlk = orc.gen_relin_key(s_ntt, 912)
+    d_rlk = hx.ckks_key_load(ctx, hx.from_host(rlk), 0)
+    rng = np.random.default_rng(913)
+    plan = orc.act_schedule(level, 2.0 ** 50)
+    cts = [orc.encrypt(rng.uniform(-1, 1, orc.n), 2.0 ** 50, level, s_ntt, 914 + i) for i in range(20)]
+    dx = [hx.from_host(ct) for ct in cts]
+    outs = [hx.empty(2, level - 3, orc.N) for _ in cts]
+    ws = hx.empty(hx.ckks_workspace_bytes(ctx, hx.binding.CKKS_OP_POLY_ACT, level, len(cts)) // 8 + 1)
+    st = torch.cuda.Stream()
+    run = lambda: hx.he_poly_act_deg7(ctx, dx, level, plan["k"], d_rlk, outs=outs, ws=ws, merged=True, stream=st.cuda_stream)
+    with torch.cuda.stream(st):
+        run()
+        st.synchronize()
+        ref = [o.clone() for o in outs]
+        for i in (0, 9, 19):
+            assert np.array_equal(hx.to_host(ref[i]), orc.poly_activation_merged(cts[i], level, plan["k"], rlk))
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=st):
+            run()
+        for _ in range(3):
+            for o in outs:
+                o.zero_()
+            torch.randn(1 << 16, device="cuda").sum().item()      # eager work and a synchronisation between replays
+            graph.replay()
+            torch.cuda.synchronize()
+            assert all(torch.equal(a, b) for a, b in zip(outs, ref))
+
+
 # --------------------------------------------------------------------------------- staged keys
 @pytest.mark.parametrize("log_n,num_q,num_p,dnum,bits", [(12, 4, 2, 2, 50), (10, 3, 1, 3, 57), (5, 3, 1, 2, 12)])
 def test_key_expansion_matches_oracle(log_n, num_q, num_p, dnum, bits):
