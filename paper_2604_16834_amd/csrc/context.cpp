@@ -69,6 +69,9 @@ extern "C" void ckks_ctx_destroy(ckks_ctx* c) {
     (void)hipFree(c->d_modup);
     (void)hipFree(c->d_moddown);
     (void)hipFree(c->d_moddown_rs);
+    (void)hipFree(c->d_modup_f);
+    (void)hipFree(c->d_moddown_f);
+    (void)hipFree(c->d_moddown_rs_f);
     (void)hipFree(c->d_rescale);
     if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
     if (c->ev_join) (void)hipEventDestroy(c->ev_join);
@@ -269,6 +272,39 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
             }
         }
     }
+    // the conversion constants as doubles (value, value / target modulus) for the double-precision conversions
+    std::vector<TwF> modup_f, moddown_f, moddown_rs_f;
+    if (c->dnum && c->ntt_f64) {
+        const u32 nq = c->num_q;
+        modup_f.assign((size_t)nq * c->dnum * M * c->alpha_pad, TwF{0.0, 0.0});
+        for (u32 level = 0; level < nq; level++)
+            for (u32 j = 0; j < c->live_digits(level); j++) {
+                const u64* tab = modup.data() + level * c->modup_level_stride() + j * c->modup_digit_stride();
+                TwF* tf = modup_f.data() + ((size_t)level * c->dnum + j) * M * c->alpha_pad;
+                for (u32 e = 0; e < c->ext_limbs(level); e++) {
+                    const double qt = (double)c->mod[c->ext_modulus(level, e)];
+                    for (u32 a = 0; a < c->alpha_pad; a++) {
+                        const double w = (double)tab[2 * c->alpha_pad + (size_t)e * c->alpha_pad + a];
+                        tf[(size_t)e * c->alpha_pad + a] = TwF{w, w / qt};
+                    }
+                }
+            }
+        moddown_f.assign((size_t)nq * c->k_pad, TwF{0.0, 0.0});
+        for (u32 i = 0; i < nq; i++)
+            for (u32 a = 0; a < c->k_pad; a++) {
+                const double w = (double)moddown[2 * c->k_pad + (size_t)i * c->k_pad + a];
+                moddown_f[(size_t)i * c->k_pad + a] = TwF{w, w / (double)c->mod[i]};
+            }
+        moddown_rs_f.assign((size_t)nq * nq * c->k2_pad, TwF{0.0, 0.0});
+        for (u32 l = 1; l < nq; l++) {
+            const u64* tab = moddown_rs.data() + l * c->moddown_rs_stride();
+            for (u32 i = 0; i < l; i++)
+                for (u32 a = 0; a < c->k2_pad; a++) {
+                    const double w = (double)tab[2 * c->k2_pad + (size_t)i * c->k2_pad + a];
+                    moddown_rs_f[((size_t)l * nq + i) * c->k2_pad + a] = TwF{w, w / (double)c->mod[i]};
+                }
+        }
+    }
     // rescale table [l][i] = (q_l^-1 mod q_i, Shoup companion, q_l mod q_i)
     std::vector<u64> resc((size_t)c->num_q * c->num_q * 3, 0);
     for (u32 l = 0; l < c->num_q; l++)
@@ -290,6 +326,9 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
     if (e == hipSuccess) e = upload(modup, &c->d_modup);
     if (e == hipSuccess) e = upload(moddown, &c->d_moddown);
     if (e == hipSuccess) e = upload(moddown_rs, &c->d_moddown_rs);
+    if (e == hipSuccess) e = upload(modup_f, &c->d_modup_f);
+    if (e == hipSuccess) e = upload(moddown_f, &c->d_moddown_f);
+    if (e == hipSuccess) e = upload(moddown_rs_f, &c->d_moddown_rs_f);
     if (e == hipSuccess) e = upload(resc, &c->d_rescale);
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {

@@ -124,6 +124,13 @@ struct ckks_ctx {
     u64* d_moddown_rs = nullptr;      // per level l >= 1, the same layout (k_pad -> k2_pad) for the dropped set {q_l, p_0..p_{k-1}}:
                                       // ModDown and rescale as one division by P*q_l; see moddown_rs_table()
     u64* d_rescale = nullptr;         // [num_q][num_q][3]: (q_l^-1 mod q_i, its Shoup companion, q_l mod q_i)
+    // The conversion constants once more as doubles (w, w / q_target), for the double-precision base conversions that
+    // contexts with ntt_f64 use: same row layout as the integer tables, one TwF per entry.
+    TwF* d_modup_f = nullptr;         // [level][digit][M positions e][alpha_pad]
+    TwF* d_moddown_f = nullptr;       // [num_q][k_pad]
+    TwF* d_moddown_rs_f = nullptr;    // [level][num_q][k2_pad]
+    const TwF* modup_table_f(u32 level, u32 j) const { return d_modup_f + ((size_t)level * dnum + j) * M * alpha_pad; }
+    const TwF* moddown_rs_table_f(u32 level) const { return d_moddown_rs_f + (size_t)level * num_q * k2_pad; }
 
     // A second stream of the library's own (default priority) with the two events of a fork/join: operations made of
     // independent channel batches put every other batch on it, so that kernels bound by arithmetic overlap with

@@ -13,6 +13,7 @@
 //              u[i] = (v[q_i] - w[i]) * P^-1  (+ an optional addend)
 // Sums of products are accumulated unreduced in 128 bits and reduced once.
 #include "ctx.h"
+#include "f64mod.h"
 #include "galois.h"
 
 #define KS_THREADS 256
@@ -103,6 +104,50 @@ __global__ __launch_bounds__(KS_THREADS) void modup_conv50_kernel(const u64* __r
     }
 }
 
+// ModUp for moduli below 2^50 in double precision: the centred residues of the digit as doubles, every term reduced by
+// an exact fused-multiply-add product (f64mod.h), the sum of at most 8 terms (below 2^53) reduced once.  About 60
+// full-rate instructions per target residue where the split integer sum takes about 90; no correction for the negative
+// terms is needed, their representatives are negative doubles.  convf: [E][AP] (constant, constant / target modulus).
+template <int AP>
+__global__ __launch_bounds__(KS_THREADS) void modup_conv_f64_kernel(const u64* __restrict__ y, size_t y_bstride, PtrList8 c_list,
+                                                                    u64* __restrict__ digit, size_t digit_bstride,
+                                                                    const u64* __restrict__ tab, const TwF* __restrict__ convf,
+                                                                    const ModConst* __restrict__ mc, const ModConstF* __restrict__ mcf,
+                                                                    u32 N, u32 level, u32 num_q, u32 lo, u32 nd, u32 E, u32 lpb) {
+    const u32 x = blockIdx.x * KS_THREADS + threadIdx.x;
+    if (x >= N) return;
+    y += blockIdx.z * y_bstride;
+    digit += blockIdx.z * digit_bstride;
+    const u64* __restrict__ c_in = c_list.p[blockIdx.z];
+    double yd[AP];
+#pragma unroll
+    for (u32 a = 0; a < AP; a++) {
+        yd[a] = 0.0;
+        if (a < nd) {
+            const u64 qa = mc[lo + a].q;
+            const u64 v = mul_shoup(y[(size_t)a * N + x], tab[a], tab[AP + a], qa);
+            yd[a] = v > (qa >> 1) ? -f64m_from_u64(qa - v) : f64m_from_u64(v);
+        }
+    }
+    const u32 e0 = blockIdx.y * lpb;
+    for (u32 e = e0; e < e0 + lpb && e < E; e++) {
+        const u32 t = e <= level ? e : num_q + (e - level - 1);
+        if (t >= lo && t < lo + nd) {
+            digit[(size_t)e * N + x] = c_in[(size_t)t * N + x];
+            continue;
+        }
+        const TwF* ce = (const TwF*)__builtin_assume_aligned(convf + (size_t)e * AP, 16 * AP);
+        const double q = mcf[t].q, qinv = mcf[t].qinv;
+        double s = 0.0;
+#pragma unroll
+        for (u32 a = 0; a < AP; a++) {
+            s += f64m_mulmod(yd[a], ce[a].w, ce[a].wq, q);
+            if (a == 7 && AP > 8) s = f64m_reduce(s, q, qinv);  // keeps longer sums below 2^53
+        }
+        digit[(size_t)e * N + x] = f64m_canonical(f64m_reduce(s, q, qinv), q);
+    }
+}
+
 // n <= KS_MAX_BATCH polynomials at once: item b reads y + b*y_bstride and c_in.p[b], writes digit + b*digit_bstride
 hipError_t launch_modup_conv(const ckks_ctx* c, u32 level, u32 j, const u64* y, size_t y_bstride, const PtrList8& c_in, u64* digit,
                              size_t digit_bstride, u32 n, hipStream_t st) {
@@ -114,7 +159,15 @@ hipError_t launch_modup_conv(const ckks_ctx* c, u32 level, u32 j, const u64* y, 
     dim3 grid(x_wgs, (E + lpb - 1) / lpb, n);
     const u64* tab = c->modup_table(level, j);
     ProfScope ps__(c, K_MODUP_CONV, st, 8.0 * n * c->N * (2.0 * nd + E), (double)n * c->N * nd * (1.0 + E - nd));
-    if (c->small_q) {
+    if (c->ntt_f64 && c->d_modup_f) {
+        const TwF* tf = c->modup_table_f(level, j);
+        if (c->alpha_pad == 4)
+            hipLaunchKernelGGL(modup_conv_f64_kernel<4>, grid, dim3(KS_THREADS), 0, st, y, y_bstride, c_in, digit, digit_bstride, tab, tf, c->d_mc, c->d_mcf, c->N, level, c->num_q, lo, nd, E, lpb);
+        else if (c->alpha_pad == 8)
+            hipLaunchKernelGGL(modup_conv_f64_kernel<8>, grid, dim3(KS_THREADS), 0, st, y, y_bstride, c_in, digit, digit_bstride, tab, tf, c->d_mc, c->d_mcf, c->N, level, c->num_q, lo, nd, E, lpb);
+        else
+            hipLaunchKernelGGL(modup_conv_f64_kernel<16>, grid, dim3(KS_THREADS), 0, st, y, y_bstride, c_in, digit, digit_bstride, tab, tf, c->d_mc, c->d_mcf, c->N, level, c->num_q, lo, nd, E, lpb);
+    } else if (c->small_q) {
         if (c->alpha_pad == 4)
             hipLaunchKernelGGL(modup_conv50_kernel<4>, grid, dim3(KS_THREADS), 0, st, y, y_bstride, c_in, digit, digit_bstride, tab, c->d_mc, c->N, level, c->num_q, lo, nd, c->M, E, lpb);
         else if (c->alpha_pad == 8)
@@ -594,6 +647,40 @@ __global__ __launch_bounds__(KS_THREADS) void moddown_conv50_kernel(const u64* _
     }
 }
 
+// The same conversion in double precision (see modup_conv_f64_kernel).  phf: [num_q][KP] (constant, constant / q_i).
+template <int KP, int KR = KP>
+__global__ __launch_bounds__(KS_THREADS) void moddown_conv_f64_kernel(const u64* __restrict__ v, u64* __restrict__ w,
+                                                                      const u64* __restrict__ tab, const TwF* __restrict__ phf,
+                                                                      const ModConst* __restrict__ mc, const ModConstF* __restrict__ mcf,
+                                                                      u32 N, u32 level, u32 num_q, u32 k, u32 E, u32 first, u32 n_out,
+                                                                      bool merged, u32 lpb) {
+    const u32 x = blockIdx.x * KS_THREADS + threadIdx.x;
+    if (x >= N) return;
+    const u32 comp = blockIdx.z;
+    double z[KR];
+#pragma unroll
+    for (u32 a = 0; a < KR; a++) {
+        z[a] = 0.0;
+        if (a < k) {
+            const u64 pa = mc[dropped_modulus(a, level, num_q, merged)].q;
+            const u64 zv = mul_shoup(v[((size_t)comp * E + first + a) * N + x], tab[a], tab[KP + a], pa);
+            z[a] = zv > (pa >> 1) ? -f64m_from_u64(pa - zv) : f64m_from_u64(zv);
+        }
+    }
+    const u32 i0 = blockIdx.y * lpb;
+    for (u32 i = i0; i < i0 + lpb && i < n_out; i++) {
+        const TwF* pe = phf + (size_t)i * KP;
+        const double q = mcf[i].q, qinv = mcf[i].qinv;
+        double s = 0.0;
+#pragma unroll
+        for (u32 a = 0; a < KR; a++) {
+            s += f64m_mulmod(z[a], pe[a].w, pe[a].wq, q);
+            if (a == 7 && KR > 8) s = f64m_reduce(s, q, qinv);
+        }
+        w[((size_t)comp * n_out + i) * N + x] = f64m_canonical(f64m_reduce(s, q, qinv), q);
+    }
+}
+
 hipError_t launch_moddown_conv(const ckks_ctx* c, u32 level, bool merged, const u64* v, u64* w, u32 batch, hipStream_t st) {
     const u32 n_out = merged ? level : level + 1, k = merged ? c->num_p + 1 : c->num_p, kp = merged ? c->k2_pad : c->k_pad;
     const u32 first = merged ? level : level + 1, E = c->ext_limbs(level);
@@ -602,6 +689,17 @@ hipError_t launch_moddown_conv(const ckks_ctx* c, u32 level, bool merged, const 
     const u32 lpb = x_wgs * batch >= 2048 ? 12 : 6;  // as in launch_modup_conv
     dim3 grid(x_wgs, (n_out + lpb - 1) / lpb, batch);
     ProfScope ps__(c, K_MODDOWN_CONV, st, 8.0 * batch * c->N * (k + n_out), 1.0 * batch * c->N * k * (n_out + 1.0));
+    if (c->ntt_f64 && c->d_moddown_f) {
+        const TwF* pf = merged ? c->moddown_rs_table_f(level) : c->d_moddown_f;
+#define MD_F64(KP_, KR_) hipLaunchKernelGGL((moddown_conv_f64_kernel<KP_, KR_>), grid, dim3(KS_THREADS), 0, st, v, w, tab, pf, c->d_mc, c->d_mcf, c->N, level, c->num_q, k, E, first, n_out, merged, lpb)
+        if (kp == 4) MD_F64(4, 4);
+        else if (kp == 8) MD_F64(8, 8);
+        else if (kp == 12 && k == 9) MD_F64(12, 9);
+        else if (kp == 12) MD_F64(12, 12);
+        else MD_F64(16, 16);
+#undef MD_F64
+        return hipGetLastError();
+    }
     if (c->small_q) {
         if (kp == 4)
             hipLaunchKernelGGL(moddown_conv50_kernel<4>, grid, dim3(KS_THREADS), 0, st, v, w, tab, c->d_mc, c->N, level, c->num_q, k, E, first, n_out, merged, lpb);
