@@ -76,7 +76,18 @@ bool level_ok(const ckks_ctx* c, u32 level) { return level < c->num_q; }
 struct KsWs {
     u64 *y, *digits, *v, *w;
     size_t y_b, dig_b, v_b, w_b;  // per-item strides in elements
+    mutable const u64* own[CT_BATCH] = {};  // the polynomials run_modup decomposed last (the digits' own limbs stay there)
 };
+// the digits of items b0, b0 + 1, ... of the batch in ws, as the inner-product kernels take them
+DigitSrc dsrc(const ckks_ctx* c, const KsWs& ws, u32 b0) {
+    DigitSrc d;
+    d.digits = ws.digits + b0 * ws.dig_b;
+    d.bstride = ws.dig_b;
+    for (u32 b = 0; b < KS_MAX_BATCH; b++) d.own.p[b] = b0 + b < CT_BATCH ? ws.own[b0 + b] : nullptr;
+    d.alpha = c->alpha;
+    d.pad = 0;
+    return d;
+}
 size_t ws_ks(const ckks_ctx* c, u32 level, u32 n_dig, u32 n_v) {
     const size_t N = c->N, L1 = level + 1, E = c->ext_limbs(level), beta = c->live_digits(level);
     return blk(n_dig * L1 * N) + blk(n_dig * beta * E * N) + blk(n_v * 2 * E * N) + blk(n_v * 2 * L1 * N);
@@ -100,6 +111,7 @@ size_t ws_ctct(const ckks_ctx* c, u32 level, u32 n) { return 3 * blk((size_t)n *
 // ws.digits + b*ws.dig_b ([beta][E][N], NTT form).
 int run_modup(const ckks_ctx* c, u32 level, const u64* const* srcs, u32 n, const KsWs& ws, hipStream_t st) {
     const u32 N = c->N, L1 = level + 1, E = c->ext_limbs(level), beta = c->live_digits(level);
+    for (u32 b = 0; b < CT_BATCH; b++) ws.own[b] = b < n ? srcs[b] : nullptr;
     // all live limbs of every polynomial to coefficient form at once
     HIP_TRY(launch_ntt(c, true, nullptr, 0, ws.y, L1, range_list(0, L1, 0), n, st, srcs));
     const PtrList8 cl = ptr_list(srcs, n);
@@ -209,7 +221,7 @@ int run_ctct(const ckks_ctx* c, u32 level, const u64* const* a, size_t a_cstride
     }
     int rc = run_modup(c, level, d2s, n, ws, st);
     if (rc) return rc;
-    HIP_TRY(launch_key_inner_multi(c, level, ws.digits, ws.dig_b, d_rlk, 1, ws.v, ws.v_b, n, st));
+    HIP_TRY(launch_key_inner_multi(c, level, dsrc(c, ws, 0), d_rlk, 1, ws.v, ws.v_b, n, st));
     return run_moddown(c, level, ws, n, items, st);
 }
 
@@ -238,7 +250,7 @@ int run_ctct_merged(const ckks_ctx* c, u32 level, const u64* const* a, size_t a_
     }
     int rc = run_modup(c, level, d2s, n, ws, st);
     if (rc) return rc;
-    HIP_TRY(launch_key_inner_ext(c, level, ws.digits, ws.dig_b, d_rlk, 1, add0, add1, nullptr, vs, n, st));
+    HIP_TRY(launch_key_inner_ext(c, level, dsrc(c, ws, 0), d_rlk, 1, add0, add1, nullptr, vs, n, st));
     return run_moddown(c, level, ws, n, items, st, true);
 }
 
@@ -341,13 +353,13 @@ int conv_deferred(const ckks_ctx* c, const he_conv_desc* d, const u32* gs, const
             ttap[n_taps++] = t;
         }
         if (fused_taps) {
-            HIP_TRY(launch_key_inner_taps(c, level, ws.digits, ws.dig_b, tkeys, tg, tmasks, ttap, n_taps, in, xs, xl, c0 * 9, 9, n, kscratch,
+            HIP_TRY(launch_key_inner_taps(c, level, dsrc(c, ws, 0), tkeys, tg, tmasks, ttap, n_taps, in, xs, xl, c0 * 9, 9, n, kscratch,
                                           c0 == 0, st, centre_mask, centre_tap));  // the masked keys are made once, by the first batch
         } else {  // many digits: one launch per tap (classic layout: every term is a [2][E][N] array)
             for (u32 i = 0; i < n_taps; i++) {
                 u64* outs[CT_BATCH];
                 for (u32 b = 0; b < n; b++) outs[b] = xs + ((size_t)(c0 + b) * 9 + ttap[i]) * x_elems;
-                HIP_TRY(launch_key_inner_ext(c, level, ws.digits, ws.dig_b, tkeys[i], tg[i], in, nullptr, tmasks[i], outs, n, st));
+                HIP_TRY(launch_key_inner_ext(c, level, dsrc(c, ws, 0), tkeys[i], tg[i], in, nullptr, tmasks[i], outs, n, st));
             }
         }
         return CKKS_OK;
@@ -396,9 +408,9 @@ int run_rotate_batch(const ckks_ctx* c, u32 level, u32 n, const u64* const* srcs
         u32 b1 = b0 + 1;
         while (b1 < n && keys[b1] == keys[b0]) b1++;
         if (b1 - b0 == 1)
-            HIP_TRY(launch_key_inner(c, level, ws.digits + b0 * ws.dig_b, keys[b0]->d_key, gal[b0], ws.v + b0 * ws.v_b, st));
+            HIP_TRY(launch_key_inner(c, level, dsrc(c, ws, b0), keys[b0]->d_key, gal[b0], ws.v + b0 * ws.v_b, st));
         else
-            HIP_TRY(launch_key_inner_multi(c, level, ws.digits + b0 * ws.dig_b, ws.dig_b, keys[b0]->d_key, gal[b0], ws.v + b0 * ws.v_b,
+            HIP_TRY(launch_key_inner_multi(c, level, dsrc(c, ws, b0), keys[b0]->d_key, gal[b0], ws.v + b0 * ws.v_b,
                                            ws.v_b, b1 - b0, st));
         b0 = b1;
     }
@@ -494,9 +506,9 @@ int run_relayout(const ckks_ctx* c, u32 level, u32 n_ct, const u64* const* cts, 
                     continue;
                 }
                 if (n == 1)
-                    HIP_TRY(launch_key_inner(c, level, ws.digits, lo_keys[l]->d_key, g_lo[l], ws.v + nk * ws.v_b, st));
+                    HIP_TRY(launch_key_inner(c, level, dsrc(c, ws, 0), lo_keys[l]->d_key, g_lo[l], ws.v + nk * ws.v_b, st));
                 else
-                    HIP_TRY(launch_key_inner_multi(c, level, ws.digits, ws.dig_b, lo_keys[l]->d_key, g_lo[l], ws.v + nk * ws.v_b, ws.v_b, n, st));
+                    HIP_TRY(launch_key_inner_multi(c, level, dsrc(c, ws, 0), lo_keys[l]->d_key, g_lo[l], ws.v + nk * ws.v_b, ws.v_b, n, st));
                 for (u32 b = 0; b < n; b++) items[nk++] = FinalItem{cts[c0 + b], nullptr, nullptr, r_at(b, l), g_lo[l], 0};
             }
             if (nk && (rc = run_moddown(c, level, ws, nk, items, st))) return rc;
@@ -593,7 +605,7 @@ int run_relayout_deferred(const ckks_ctx* c, u32 level, u32 n_ct, const u64* con
             if (g_lo[l] == 1) {
                 for (u32 b = 0; b < n; b++) HIP_TRY(launch_scale_p_ext(c, level, in[b], xo[b], st));
             } else {
-                HIP_TRY(launch_key_inner_ext(c, level, ws.digits, ws.dig_b, lo_keys[l]->d_key, g_lo[l], in, nullptr, nullptr, xo, n, st));
+                HIP_TRY(launch_key_inner_ext(c, level, dsrc(c, ws, 0), lo_keys[l]->d_key, g_lo[l], in, nullptr, nullptr, xo, n, st));
             }
         }
         HIP_TRY(launch_relayout_mac(c, level, true, X, masks, Vacc, n, n_lo, n_hi, st));
@@ -619,7 +631,7 @@ int run_relayout_deferred(const ckks_ctx* c, u32 level, u32 n_ct, const u64* con
             for (u32 b0 = 0; b0 < nk;) {
                 u32 b1 = b0 + 1;
                 while (b1 < nk && ks[b1] == ks[b0]) b1++;
-                HIP_TRY(launch_key_inner_ext(c, l1, ws.digits + b0 * ws.dig_b, ws.dig_b, ks[b0]->d_key, gs[b0], src + b0, nullptr, nullptr,
+                HIP_TRY(launch_key_inner_ext(c, l1, dsrc(c, ws, b0), ks[b0]->d_key, gs[b0], src + b0, nullptr, nullptr,
                                              dst + b0, b1 - b0, st));
                 b0 = b1;
             }
@@ -803,7 +815,7 @@ int ckks_keyswitch(const ckks_ctx* c, const uint64_t* d_c, uint32_t level, const
     const u64* src = (const u64*)d_c;
     int rc = run_modup(c, level, &src, 1, ws, st);
     if (rc) return rc;
-    HIP_TRY(launch_key_inner(c, level, ws.digits, key->d_key, 1, ws.v, st));
+    HIP_TRY(launch_key_inner(c, level, dsrc(c, ws, 0), key->d_key, 1, ws.v, st));
     const FinalItem item = {nullptr, nullptr, nullptr, (u64*)d_out, 1, 0};
     return run_moddown(c, level, ws, 1, &item, st);
 }
@@ -855,6 +867,7 @@ int ckks_rotate_hoisted(const ckks_ctx* c, const uint64_t* d_ct, uint32_t level,
     if (n_keyed && hoisted) {
         int rc = run_modup(c, level, &c1, 1, ws, st);
         if (rc) return rc;
+        for (u32 l = 0; l < 2; l++) lane_ws[l].own[0] = ws.own[0];  // both lanes read the same digits
     }
     if (two_lanes) {
         HIP_TRY(hipEventRecord(c->ev_fork, st));
@@ -879,7 +892,7 @@ int ckks_rotate_hoisted(const ckks_ctx* c, const uint64_t* d_ct, uint32_t level,
             // same digits, one key per rotation; the digits are read through sigma_g
             const KsWs& lw = lane_ws[lane];
             hipStream_t ls = lane ? c->side : st;
-            if (hipError_t e = launch_key_inner(c, level, lw.digits, keys[t]->d_key, g, lw.v + nb * lw.v_b, ls); e != hipSuccess)
+            if (hipError_t e = launch_key_inner(c, level, dsrc(c, lw, 0), keys[t]->d_key, g, lw.v + nb * lw.v_b, ls); e != hipSuccess)
                 return join(set_hip_err(c, e));
             items[nb] = FinalItem{c0, nullptr, nullptr, out, g, 0};
             if (++nb == rb) {
@@ -894,7 +907,7 @@ int ckks_rotate_hoisted(const ckks_ctx* c, const uint64_t* d_ct, uint32_t level,
             int rc = run_modup(c, level, &src, 1, ws, st);
             if (rc) return rc;
             // the digits already belong to sigma_g(c1): no gather in the inner product, only on c0
-            HIP_TRY(launch_key_inner(c, level, ws.digits, keys[t]->d_key, 1, ws.v, st));
+            HIP_TRY(launch_key_inner(c, level, dsrc(c, ws, 0), keys[t]->d_key, 1, ws.v, st));
             const FinalItem item = {c0, nullptr, nullptr, out, g, 0};
             if ((rc = run_moddown(c, level, ws, 1, &item, st))) return rc;
         }
@@ -996,7 +1009,7 @@ int he_conv_batched(const ckks_ctx* c, const he_conv_desc* d, const uint64_t* co
     auto slot = [&](u32 ch, u32 t) { return xs + ((size_t)ch * 9 + t) * ct_elems; };
     // rotate the batch `base` (digits already in ws) by the offset of tap `kt`; outs[b] gets mask `m`
     auto rotate_batch = [&](const u64* const* base, u32 n, u32 kt, u64* const* outs, const u64* m) -> int {
-        HIP_TRY(launch_key_inner_multi(c, level, ws.digits, ws.dig_b, rot_keys[kt]->d_key, gs[kt], ws.v, ws.v_b, n, st));
+        HIP_TRY(launch_key_inner_multi(c, level, dsrc(c, ws, 0), rot_keys[kt]->d_key, gs[kt], ws.v, ws.v_b, n, st));
         FinalItem items[CT_BATCH];
         for (u32 b = 0; b < n; b++) items[b] = FinalItem{base[b], nullptr, m, outs[b], gs[kt], 0};
         return run_moddown(c, level, ws, n, items, st);

@@ -83,6 +83,15 @@ struct FinalItem {
     u32 g;
     u32 pad;
 };
+// Where the inner-product kernels find the extended digits of batch item b: digit j, position e of the extended basis is
+// row (j*E + e) of digits + b*bstride, except for the digit's OWN limbs (e <= level, e / alpha == j), which ModUp does not
+// copy: they are the limbs of the decomposed polynomial itself, own.p[b] ([level+1][N], evaluation form).
+struct DigitSrc {
+    const u64* digits;
+    size_t bstride;
+    PtrList8 own;
+    u32 alpha, pad;
+};
 struct FinalBatch {
     FinalItem it[KS_MAX_BATCH];
 };
@@ -195,16 +204,16 @@ inline bool ntt_has_epilogue(const ckks_ctx* c) { return c->log_n > CKKS_TILE_LO
 // keyswitch.hip
 hipError_t launch_modup_conv(const ckks_ctx* c, u32 level, u32 j, const u64* y, size_t y_bstride, const PtrList8& c_in, u64* digit,
                              size_t digit_bstride, u32 n, hipStream_t st);
-hipError_t launch_key_inner(const ckks_ctx* c, u32 level, const u64* digits, const u64* key, u32 g, u64* v, hipStream_t st);
-hipError_t launch_key_inner_multi(const ckks_ctx* c, u32 level, const u64* digits, size_t digits_bstride, const u64* key, u32 g,
+hipError_t launch_key_inner(const ckks_ctx* c, u32 level, const DigitSrc& digits, const u64* key, u32 g, u64* v, hipStream_t st);
+hipError_t launch_key_inner_multi(const ckks_ctx* c, u32 level, const DigitSrc& digits, const u64* key, u32 g,
                                   u64* v, size_t v_bstride, u32 n, hipStream_t st);
 // add0s / add1s: per item, polynomials [level+1][N] whose P-fold is added to component 0 / 1 (either list, or entries, may be null)
-hipError_t launch_key_inner_ext(const ckks_ctx* c, u32 level, const u64* digits, size_t digits_bstride, const u64* key, u32 g,
+hipError_t launch_key_inner_ext(const ckks_ctx* c, u32 level, const DigitSrc& digits, const u64* key, u32 g,
                                 const u64* const* add0s, const u64* const* add1s, const u64* mask, u64* const* outs, u32 n,
                                 hipStream_t st);
 // result of (item b, tap i) = term k0 + b*k_bstride + taps[i] of `xs` in layout xl; c0s[b] = the whole ciphertext
 // [2][level+1][N]; centre_mask (optional, [E][N]): the tap without a rotation, written as term centre_tap
-hipError_t launch_key_inner_taps(const ckks_ctx* c, u32 level, const u64* digits, size_t digits_bstride, const u64* const* keys,
+hipError_t launch_key_inner_taps(const ckks_ctx* c, u32 level, const DigitSrc& digits, const u64* const* keys,
                                  const u32* gs, const u64* const* masks, const u32* taps, u32 n_taps, const u64* const* c0s,
                                  u64* xs, XLayout xl, u32 k0, u32 k_bstride, u32 n, u64* scratch, bool prepare, hipStream_t st,
                                  const u64* centre_mask = nullptr, u32 centre_tap = 0);

@@ -19,6 +19,12 @@
 #define KS_THREADS 256
 #define KS_MAX_DIGIT 16  // limbs per digit / special primes handled in registers
 
+// row [N] of (batch item b, digit j, extended-basis position e): see DigitSrc
+__device__ __forceinline__ const u64* digit_row(const DigitSrc& D, u32 b, u32 j, u32 e, u32 E, u32 N, u32 level) {
+    if (e <= level && e / D.alpha == j) return D.own.p[b] + (size_t)e * N;
+    return D.digits + b * D.bstride + ((size_t)j * E + e) * N;
+}
+
 // ---- ModUp: basis extension of one digit --------------------------------------------------------
 // y     [nd][N]      digit limbs in coefficient form (canonical)
 // c_in  [level+1][N] the polynomial being switched, NTT form (source of the digit's own limbs)
@@ -45,10 +51,7 @@ __global__ __launch_bounds__(KS_THREADS) void modup_conv_kernel(const u64* __res
     const u32 e0 = blockIdx.y * lpb;
     for (u32 e = e0; e < e0 + lpb && e < E; e++) {
         const u32 t = e <= level ? e : num_q + (e - level - 1);
-        if (t >= lo && t < lo + nd) {
-            digit[(size_t)e * N + x] = c_in[(size_t)t * N + x];
-            continue;
-        }
+        if (t >= lo && t < lo + nd) continue;  // the digit's own limbs are read from the polynomial itself (DigitSrc)
         U128 acc = {0, 0};
 #pragma unroll
         for (u32 a = 0; a < KS_MAX_DIGIT; a++)
@@ -87,10 +90,7 @@ __global__ __launch_bounds__(KS_THREADS) void modup_conv50_kernel(const u64* __r
     const u32 e0 = blockIdx.y * lpb;
     for (u32 e = e0; e < e0 + lpb && e < E; e++) {
         const u32 t = e <= level ? e : num_q + (e - level - 1);
-        if (t >= lo && t < lo + nd) {
-            digit[(size_t)e * N + x] = c_in[(size_t)t * N + x];
-            continue;
-        }
+        if (t >= lo && t < lo + nd) continue;  // the digit's own limbs are read from the polynomial itself (DigitSrc)
         const u64* ce = (const u64*)__builtin_assume_aligned(conv + (size_t)e * AP, 8 * AP);
         u64 cv[AP];
 #pragma unroll
@@ -132,10 +132,7 @@ __global__ __launch_bounds__(KS_THREADS) void modup_conv_f64_kernel(const u64* _
     const u32 e0 = blockIdx.y * lpb;
     for (u32 e = e0; e < e0 + lpb && e < E; e++) {
         const u32 t = e <= level ? e : num_q + (e - level - 1);
-        if (t >= lo && t < lo + nd) {
-            digit[(size_t)e * N + x] = c_in[(size_t)t * N + x];
-            continue;
-        }
+        if (t >= lo && t < lo + nd) continue;  // the digit's own limbs are read from the polynomial itself (DigitSrc)
         const TwF* ce = (const TwF*)__builtin_assume_aligned(convf + (size_t)e * AP, 16 * AP);
         const double q = mcf[t].q, qinv = mcf[t].qinv;
         double s = 0.0;
@@ -183,7 +180,7 @@ hipError_t launch_modup_conv(const ckks_ctx* c, u32 level, u32 j, const u64* y, 
 
 // ---- inner product with the switching key ------------------------------------------------------
 // digits [beta][E][N], key [dnum][2][M][N], v [2][E][N]
-__global__ __launch_bounds__(KS_THREADS) void key_inner_kernel(const u64* __restrict__ digits, const u64* __restrict__ key,
+__global__ __launch_bounds__(KS_THREADS) void key_inner_kernel(DigitSrc digits, const u64* __restrict__ key,
                                                                u64* __restrict__ v, const ModConst* __restrict__ mc, u32 log_n,
                                                                u32 level, u32 num_q, u32 M, u32 E, u32 beta, u32 g) {
     const u32 N = 1u << log_n;
@@ -195,7 +192,7 @@ __global__ __launch_bounds__(KS_THREADS) void key_inner_kernel(const u64* __rest
     U128 acc0 = {0, 0}, acc1 = {0, 0};
     const ModConst m = mc[t];
     for (u32 j = 0; j < beta; j++) {
-        const u64 d = digits[((size_t)j * E + e) * N + xs];
+        const u64 d = digit_row(digits, 0, j, e, E, N, level)[xs];
         acc_wide(acc0, d, key[(((size_t)j * 2 + 0) * M + t) * N + x]);
         acc_wide(acc1, d, key[(((size_t)j * 2 + 1) * M + t) * N + x]);
         if ((j & 15) == 15) {  // keep the unreduced sums inside the Barrett input range
@@ -207,7 +204,7 @@ __global__ __launch_bounds__(KS_THREADS) void key_inner_kernel(const u64* __rest
     v[((size_t)1 * E + e) * N + x] = barrett_reduce(acc1, m);
 }
 
-hipError_t launch_key_inner(const ckks_ctx* c, u32 level, const u64* digits, const u64* key, u32 g, u64* v, hipStream_t st) {
+hipError_t launch_key_inner(const ckks_ctx* c, u32 level, const DigitSrc& digits, const u64* key, u32 g, u64* v, hipStream_t st) {
     const u32 E = c->ext_limbs(level);
     dim3 grid((c->N + KS_THREADS - 1) / KS_THREADS, E);
     { ProfScope ps__(c, K_KEY_INNER, st, 8.0 * c->N * E * (3.0 * c->live_digits(level) + 2.0), 2.0 * c->N * E * c->live_digits(level)); hipLaunchKernelGGL(key_inner_kernel, grid, dim3(KS_THREADS), 0, st, digits, key, v, c->d_mc, c->log_n, level, c->num_q,
@@ -219,8 +216,7 @@ hipError_t launch_key_inner(const ckks_ctx* c, u32 level, const u64* digits, con
 // rotation and relinearisation keys): every thread keeps its key words while it walks the batch, so
 // the key streams from HBM once per batch instead of once per key switch.
 // digits + b*digits_bstride: [beta][E][N];  v + b*v_bstride: [2][E][N]
-__global__ __launch_bounds__(KS_THREADS) void key_inner_multi_kernel(const u64* __restrict__ digits, size_t digits_bstride,
-                                                                     const u64* __restrict__ key, u64* __restrict__ v,
+__global__ __launch_bounds__(KS_THREADS) void key_inner_multi_kernel(DigitSrc digits, const u64* __restrict__ key, u64* __restrict__ v,
                                                                      size_t v_bstride, const ModConst* __restrict__ mc, u32 log_n,
                                                                      u32 level, u32 num_q, u32 M, u32 E, u32 beta, u32 g, u32 n) {
     const u32 N = 1u << log_n;
@@ -239,11 +235,10 @@ __global__ __launch_bounds__(KS_THREADS) void key_inner_multi_kernel(const u64* 
             k1[j] = j < beta ? key[(((size_t)j * 2 + 1) * M + t) * N + x] : 0;
         }
         for (u32 b = 0; b < n; b++) {
-            const u64* d = digits + b * digits_bstride;
             U128 acc0 = {0, 0}, acc1 = {0, 0};
 #pragma unroll
             for (u32 j = 0; j < 4; j++) {
-                const u64 dv = j < beta ? d[((size_t)j * E + e) * N + xs] : 0;
+                const u64 dv = j < beta ? digit_row(digits, b, j, e, E, N, level)[xs] : 0;
                 acc_wide(acc0, dv, k0[j]);
                 acc_wide(acc1, dv, k1[j]);
             }
@@ -254,10 +249,9 @@ __global__ __launch_bounds__(KS_THREADS) void key_inner_multi_kernel(const u64* 
         return;
     }
     for (u32 b = 0; b < n; b++) {
-        const u64* d = digits + b * digits_bstride;
         U128 acc0 = {0, 0}, acc1 = {0, 0};
         for (u32 j = 0; j < beta; j++) {
-            const u64 dv = d[((size_t)j * E + e) * N + xs];
+            const u64 dv = digit_row(digits, b, j, e, E, N, level)[xs];
             acc_wide(acc0, dv, key[(((size_t)j * 2 + 0) * M + t) * N + x]);
             acc_wide(acc1, dv, key[(((size_t)j * 2 + 1) * M + t) * N + x]);
             if ((j & 15) == 15) {
@@ -271,12 +265,12 @@ __global__ __launch_bounds__(KS_THREADS) void key_inner_multi_kernel(const u64* 
     }
 }
 
-hipError_t launch_key_inner_multi(const ckks_ctx* c, u32 level, const u64* digits, size_t digits_bstride, const u64* key, u32 g,
+hipError_t launch_key_inner_multi(const ckks_ctx* c, u32 level, const DigitSrc& digits, const u64* key, u32 g,
                                   u64* v, size_t v_bstride, u32 n, hipStream_t st) {
     const u32 E = c->ext_limbs(level), beta = c->live_digits(level);
     dim3 grid((c->N + KS_THREADS - 1) / KS_THREADS, E);
     ProfScope ps__(c, K_KEY_INNER, st, 8.0 * c->N * E * (2.0 * beta + n * (beta + 2.0)), 2.0 * n * c->N * E * beta);
-    hipLaunchKernelGGL(key_inner_multi_kernel, grid, dim3(KS_THREADS), 0, st, digits, digits_bstride, key, v, v_bstride, c->d_mc,
+    hipLaunchKernelGGL(key_inner_multi_kernel, grid, dim3(KS_THREADS), 0, st, digits, key, v, v_bstride, c->d_mc,
                        c->log_n, level, c->num_q, c->M, E, beta, g, n);
     return hipGetLastError();
 }
@@ -294,8 +288,7 @@ struct ExtItems {
     u64* out[KS_MAX_BATCH];
 };
 
-__global__ __launch_bounds__(KS_THREADS) void key_inner_ext_kernel(const u64* __restrict__ digits, size_t digits_bstride,
-                                                                   const u64* __restrict__ key, ExtItems items,
+__global__ __launch_bounds__(KS_THREADS) void key_inner_ext_kernel(DigitSrc digits, const u64* __restrict__ key, ExtItems items,
                                                                    const u64* __restrict__ mask, const u64* __restrict__ negp,
                                                                    const ModConst* __restrict__ mc, u32 log_n, u32 level, u32 num_q,
                                                                    u32 M, u32 E, u32 beta, u32 g, u32 n) {
@@ -319,18 +312,17 @@ __global__ __launch_bounds__(KS_THREADS) void key_inner_ext_kernel(const u64* __
         }
     }
     for (u32 b = 0; b < n; b++) {
-        const u64* d = digits + b * digits_bstride;
         U128 acc0 = {0, 0}, acc1 = {0, 0};
         if (beta <= 4) {
 #pragma unroll
             for (u32 j = 0; j < 4; j++) {
-                const u64 dv = j < beta ? d[((size_t)j * E + e) * N + xs] : 0;
+                const u64 dv = j < beta ? digit_row(digits, b, j, e, E, N, level)[xs] : 0;
                 acc_wide(acc0, dv, k0[j]);
                 acc_wide(acc1, dv, k1[j]);
             }
         } else {
             for (u32 j = 0; j < beta; j++) {
-                const u64 dv = d[((size_t)j * E + e) * N + xs];
+                const u64 dv = digit_row(digits, b, j, e, E, N, level)[xs];
                 acc_wide(acc0, dv, key[(((size_t)j * 2 + 0) * M + t) * N + x]);
                 acc_wide(acc1, dv, key[(((size_t)j * 2 + 1) * M + t) * N + x]);
                 if ((j & 15) == 15) {
@@ -354,7 +346,7 @@ __global__ __launch_bounds__(KS_THREADS) void key_inner_ext_kernel(const u64* __
 
 // add0s / add1s / outs: host arrays of n <= KS_MAX_BATCH device pointers ([level+1][N], [level+1][N], [2][E][N]);
 // add0s, add1s or single entries of them may be null
-hipError_t launch_key_inner_ext(const ckks_ctx* c, u32 level, const u64* digits, size_t digits_bstride, const u64* key, u32 g,
+hipError_t launch_key_inner_ext(const ckks_ctx* c, u32 level, const DigitSrc& digits, const u64* key, u32 g,
                                 const u64* const* add0s, const u64* const* add1s, const u64* mask, u64* const* outs, u32 n,
                                 hipStream_t st) {
     const u32 E = c->ext_limbs(level), beta = c->live_digits(level);
@@ -370,7 +362,7 @@ hipError_t launch_key_inner_ext(const ckks_ctx* c, u32 level, const u64* digits,
     dim3 grid((c->N + KS_THREADS - 1) / KS_THREADS, E);
     ProfScope ps__(c, K_KEY_INNER, st, 8.0 * c->N * (E * (2.0 * beta + (mask ? 1.0 : 0.0) + n * (beta + 2.0)) + n_add * (level + 1.0)),
                    2.0 * n * c->N * E * (beta + 1.0));
-    hipLaunchKernelGGL(key_inner_ext_kernel, grid, dim3(KS_THREADS), 0, st, digits, digits_bstride, key, items, mask, negp, c->d_mc,
+    hipLaunchKernelGGL(key_inner_ext_kernel, grid, dim3(KS_THREADS), 0, st, digits, key, items, mask, negp, c->d_mc,
                        c->log_n, level, c->num_q, c->M, E, beta, g, n);
     return hipGetLastError();
 }
@@ -420,7 +412,7 @@ __global__ __launch_bounds__(KS_THREADS) void mask_keys_kernel(TapSet T, u64* __
 
 // SMALL: every modulus below 2^50 (carry-free 25-bit-split accumulation, three multiply-adds per product).
 template <int BETA, bool SMALL>
-__global__ __launch_bounds__(KS_THREADS) void key_inner_taps_kernel(const u64* __restrict__ digits, size_t digits_bstride, TapSet T,
+__global__ __launch_bounds__(KS_THREADS) void key_inner_taps_kernel(DigitSrc digits, TapSet T,
                                                                     const u64* __restrict__ mk, const u64* __restrict__ mp,
                                                                     PtrList8 c0s, u64* __restrict__ xs, XLayout xl, u32 k0base,
                                                                     u32 k_bstride, const ModConst* __restrict__ mc, u32 log_n,
@@ -437,7 +429,7 @@ __global__ __launch_bounds__(KS_THREADS) void key_inner_taps_kernel(const u64* _
         const bool on = b < n;
         cv[b] = (on && has_add) ? c0s.p[b][(size_t)e * N + xsrc] : 0;
 #pragma unroll
-        for (u32 j = 0; j < BETA; j++) dv[b][j] = on ? digits[b * digits_bstride + ((size_t)j * E + e) * N + xsrc] : 0;
+        for (u32 j = 0; j < BETA; j++) dv[b][j] = on ? digit_row(digits, b, j, e, E, N, level)[xsrc] : 0;
     }
     for (u32 i = 0; i < T.n_taps; i++) {
         const u32 x = galois_gather_index(xsrc, T.ginv[i], log_n);  // destination point
@@ -512,7 +504,7 @@ size_t key_inner_taps_scratch_elems(const ckks_ctx* c, u32 level, u32 n_taps) {
 // c0s: n <= CT_BATCH device pointers [level+1][N]; scratch: key_inner_taps_scratch_elems() words, filled by
 // prepare (once per set of taps) and read by every later call with prepare = false.
 // Needs beta <= 4 (returns hipErrorNotSupported otherwise: the caller then falls back to one launch per tap).
-hipError_t launch_key_inner_taps(const ckks_ctx* c, u32 level, const u64* digits, size_t digits_bstride, const u64* const* keys,
+hipError_t launch_key_inner_taps(const ckks_ctx* c, u32 level, const DigitSrc& digits, const u64* const* keys,
                                  const u32* gs, const u64* const* masks, const u32* taps, u32 n_taps, const u64* const* c0s,
                                  u64* xs, XLayout xl, u32 k0, u32 k_bstride, u32 n, u64* scratch, bool prepare, hipStream_t st,
                                  const u64* centre_mask, u32 centre_tap) {
@@ -557,10 +549,10 @@ hipError_t launch_key_inner_taps(const ckks_ctx* c, u32 level, const u64* digits
 #define KI_TAPS(B_)                                                                                                                  \
     do {                                                                                                                             \
         if (c->small_q)                                                                                                              \
-            hipLaunchKernelGGL((key_inner_taps_kernel<B_, true>), grid, dim3(KS_THREADS), 0, st, digits, digits_bstride, T, mk, mp, cl, xs, xl, \
+            hipLaunchKernelGGL((key_inner_taps_kernel<B_, true>), grid, dim3(KS_THREADS), 0, st, digits, T, mk, mp, cl, xs, xl, \
                                k0, k_bstride, c->d_mc, c->log_n, level, c->num_q, E, n);                                             \
         else                                                                                                                         \
-            hipLaunchKernelGGL((key_inner_taps_kernel<B_, false>), grid, dim3(KS_THREADS), 0, st, digits, digits_bstride, T, mk, mp, cl, xs, xl, \
+            hipLaunchKernelGGL((key_inner_taps_kernel<B_, false>), grid, dim3(KS_THREADS), 0, st, digits, T, mk, mp, cl, xs, xl, \
                                k0, k_bstride, c->d_mc, c->log_n, level, c->num_q, E, n);                                             \
     } while (0)
     if (beta == 1) KI_TAPS(1);
