@@ -112,13 +112,18 @@ size_t ws_ctct(const ckks_ctx* c, u32 level, u32 n) { return 3 * blk((size_t)n *
 int run_modup(const ckks_ctx* c, u32 level, const u64* const* srcs, u32 n, const KsWs& ws, hipStream_t st) {
     const u32 N = c->N, L1 = level + 1, E = c->ext_limbs(level), beta = c->live_digits(level);
     for (u32 b = 0; b < CT_BATCH; b++) ws.own[b] = b < n ? srcs[b] : nullptr;
-    // all live limbs of every polynomial to coefficient form at once
-    HIP_TRY(launch_ntt(c, true, nullptr, 0, ws.y, L1, range_list(0, L1, 0), n, st, srcs));
+    // all live limbs of every polynomial to coefficient form at once.  With double-precision transforms the inverse scales
+    // limb i by N^-1 (Q_j/q_i)^-1 and leaves the centred residue as a double, and each digit's basis conversion happens
+    // inside the first pass of the forward transforms of its target limbs (no conversion kernel, no coefficient-form copy
+    // of the extended digit).
+    const bool fused = ntt_has_modup(c);
+    HIP_TRY(launch_ntt(c, true, nullptr, 0, ws.y, L1, range_list(0, L1, 0), n, st, srcs, nullptr,
+                       fused ? c->d_modup_prep_f + (size_t)level * c->num_q : nullptr));
     const PtrList8 cl = ptr_list(srcs, n);
     for (u32 j = 0; j < beta; j++) {
         const u32 lo = c->digit_lo(j), hi = c->digit_hi(j, level);
         u64* digit = ws.digits + (size_t)j * E * N;
-        HIP_TRY(launch_modup_conv(c, level, j, ws.y + (size_t)lo * N, ws.y_b, cl, digit, ws.dig_b, n, st));
+        if (!fused) HIP_TRY(launch_modup_conv(c, level, j, ws.y + (size_t)lo * N, ws.y_b, cl, digit, ws.dig_b, n, st));
         PolyList pl;
         pl.n = 0;
         for (u32 e = 0; e < E; e++) {
@@ -129,7 +134,8 @@ int run_modup(const ckks_ctx* c, u32 level, const u64* const* srcs, u32 n, const
             pl.n++;
         }
         for (u32 a = pl.n; a < CKKS_MAX_MODULI; a++) pl.spos[a] = pl.dpos[a] = pl.mod[a] = 0;
-        HIP_TRY(launch_ntt(c, false, digit, (size_t)beta * E, digit, (size_t)beta * E, pl, n, st));
+        if (fused) HIP_TRY(launch_ntt_modup(c, level, j, (const double*)ws.y, ws.y_b, digit, (size_t)beta * E, pl, n, st));
+        else HIP_TRY(launch_ntt(c, false, digit, (size_t)beta * E, digit, (size_t)beta * E, pl, n, st));
     }
     return CKKS_OK;
 }

@@ -70,6 +70,7 @@ extern "C" void ckks_ctx_destroy(ckks_ctx* c) {
     (void)hipFree(c->d_moddown);
     (void)hipFree(c->d_moddown_rs);
     (void)hipFree(c->d_modup_f);
+    (void)hipFree(c->d_modup_prep_f);
     (void)hipFree(c->d_moddown_f);
     (void)hipFree(c->d_moddown_rs_f);
     (void)hipFree(c->d_rescale);
@@ -273,7 +274,7 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
         }
     }
     // the conversion constants as doubles (value, value / target modulus) for the double-precision conversions
-    std::vector<TwF> modup_f, moddown_f, moddown_rs_f;
+    std::vector<TwF> modup_f, modup_prep_f, moddown_f, moddown_rs_f;
     if (c->dnum && c->ntt_f64) {
         const u32 nq = c->num_q;
         modup_f.assign((size_t)nq * c->dnum * M * c->alpha_pad, TwF{0.0, 0.0});
@@ -287,6 +288,16 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
                         const double w = (double)tab[2 * c->alpha_pad + (size_t)e * c->alpha_pad + a];
                         tf[(size_t)e * c->alpha_pad + a] = TwF{w, w / qt};
                     }
+                }
+            }
+        modup_prep_f.assign((size_t)nq * nq, TwF{0.0, 0.0});
+        for (u32 level = 0; level < nq; level++)
+            for (u32 j = 0; j < c->live_digits(level); j++) {
+                const u64* tab = modup.data() + level * c->modup_level_stride() + j * c->modup_digit_stride();
+                for (u32 i = c->digit_lo(j); i < c->digit_hi(j, level); i++) {
+                    const u64 qi = c->mod[i];
+                    const double w = (double)h_mulmod(tab[i - c->digit_lo(j)], c->mc[i].n_inv, qi);
+                    modup_prep_f[(size_t)level * nq + i] = TwF{w, w / (double)qi};
                 }
             }
         moddown_f.assign((size_t)nq * c->k_pad, TwF{0.0, 0.0});
@@ -327,6 +338,7 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
     if (e == hipSuccess) e = upload(moddown, &c->d_moddown);
     if (e == hipSuccess) e = upload(moddown_rs, &c->d_moddown_rs);
     if (e == hipSuccess) e = upload(modup_f, &c->d_modup_f);
+    if (e == hipSuccess) e = upload(modup_prep_f, &c->d_modup_prep_f);
     if (e == hipSuccess) e = upload(moddown_f, &c->d_moddown_f);
     if (e == hipSuccess) e = upload(moddown_rs_f, &c->d_moddown_rs_f);
     if (e == hipSuccess) e = upload(resc, &c->d_rescale);

@@ -136,6 +136,7 @@ struct ckks_ctx {
     // The conversion constants once more as doubles (w, w / q_target), for the double-precision base conversions that
     // contexts with ntt_f64 use: same row layout as the integer tables, one TwF per entry.
     TwF* d_modup_f = nullptr;         // [level][digit][M positions e][alpha_pad]
+    TwF* d_modup_prep_f = nullptr;    // [level][num_q]: N^-1 (Q_j/q_i)^-1 mod q_i, what the inverse transform in front of ModUp scales by
     TwF* d_moddown_f = nullptr;       // [num_q][k_pad]
     TwF* d_moddown_rs_f = nullptr;    // [level][num_q][k2_pad]
     const TwF* modup_table_f(u32 level, u32 j) const { return d_modup_f + ((size_t)level * dnum + j) * M * alpha_pad; }
@@ -198,7 +199,14 @@ struct ProfScope {
 // array of `batch` <= KS_MAX_BATCH device pointers) and writes dst + b*dst_bstride*N
 hipError_t launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, size_t src_bstride, u64* dst,
                       size_t dst_bstride, const PolyList& pl, u32 batch, hipStream_t st, const u64* const* src_ptrs = nullptr,
-                      const FwdEpilogue* epilogue = nullptr);
+                      const FwdEpilogue* epilogue = nullptr, const TwF* inv_scale = nullptr);
+// ModUp fused into transforms (contexts with ntt_f64 and the two-pass transform): the inverse transform of the polynomial
+// scales limb i by inv_scale[i] instead of 1/N and stores the CENTRED residue as a double (launch_ntt with inv_scale);
+// launch_ntt_modup then evaluates the basis conversion of digit j, y [batch][level+1][N] doubles -> the pl.n target limbs
+// pl.dpos[] of dst (batch stride dst_bstride limb-polys), inside the first pass of their forward transforms.
+inline bool ntt_has_modup(const ckks_ctx* c) { return c->ntt_f64 && c->log_n > CKKS_TILE_LOG && c->d_modup_prep_f != nullptr; }
+hipError_t launch_ntt_modup(const ckks_ctx* c, u32 level, u32 j, const double* y, size_t y_bstride, u64* dst, size_t dst_bstride,
+                            const PolyList& pl, u32 batch, hipStream_t st);
 // whether launch_ntt can apply an epilogue in this ring (it needs the two-pass transform)
 inline bool ntt_has_epilogue(const ckks_ctx* c) { return c->log_n > CKKS_TILE_LOG; }
 // keyswitch.hip

@@ -29,6 +29,8 @@
 //             an inverse butterfly, so every multiplicand stays below 2q < 2^51 and every sum below 2^53:
 //             all arithmetic is exact.  Between the two passes the data sit in HBM as doubles.
 // Rings below 2^11 use a plain one-tile integer kernel.
+#include <type_traits>
+
 #include "ctx.h"
 #include "galois.h"
 
@@ -196,6 +198,8 @@ struct NttArgs {
     u32 lo_group;        // slices per group of the lo-pass numbering (0: plain)
     u32 use_src_list;    // batch item b reads src_list.p[b] instead of src + b*src_bstride*N
     PtrList8 src_list;
+    const TwF* inv_scale;  // inverse, last pass (double-precision arithmetic): limb at position p is scaled by inv_scale[p]
+                           // instead of 1/N and stored as the centred residue in a double (the form ModUp's conversion reads)
 };
 
 // Lo-pass workgroups are numbered in groups of `grp` consecutive (limb, block) slices, batch item by
@@ -503,6 +507,103 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_hi_kernel(NttArgs args, P
     }
 }
 
+// The forward hi pass with ModUp's basis conversion in front of it: the points of target limb e (position pl.dpos[a]) are
+//   sum_i yhat_i * [Q_j/q_i]_{q_e}  mod q_e
+// evaluated from the digit's centred residues yhat (doubles, [batch][level+1][N]) as the tile is loaded: the converted
+// polynomial is never written in coefficient form.  convf: [E][AP] (constant, constant / q_e); lo, nd: the digit's limbs.
+struct ConvPrologue {
+    const double* y;
+    size_t y_bstride;  // elements
+    const TwF* convf;
+    u32 lo, nd;
+};
+
+template <int AP>
+__device__ __forceinline__ double conv_point(const double* __restrict__ yp, size_t N, u32 nd, const TwF* cw, double q, double qinv) {
+    // no branch around the loads: entries beyond the digit's nd limbs re-read its last limb against a zero constant
+    double yv[AP];
+#pragma unroll
+    for (int a = 0; a < AP; a++) yv[a] = yp[(size_t)((u32)a < nd ? a : nd - 1) * N];
+    double s = 0.0;
+#pragma unroll
+    for (int a = 0; a < AP; a++) {
+        s += ArithF64::mulmod(yv[a], cw[a].w, cw[a].wq, q);
+        if (a == 7 && AP > 8) s = __builtin_fma(-ArithF64::round_mul(s, qinv), q, s);  // keeps longer sums below 2^53
+    }
+    return __builtin_fma(-ArithF64::round_mul(s, qinv), q, s);
+}
+
+template <int LOG_HI, int AP>
+__global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_hi_conv_kernel(NttArgs args, PolyList pl, ConvPrologue cp) {
+    typedef ArithF64 A;
+    typedef double E;
+    constexpr int R = 1 << LOG_HI, CC = NTT_TILE / R;
+    const u32 tid = threadIdx.x, tile = blockIdx.x, b = blockIdx.y / pl.n, a_idx = blockIdx.y % pl.n;
+    const PolyRef<A> P = poly_ref<A>(args, pl, b, a_idx);
+    const size_t N = (size_t)1 << args.log_n;
+    const double* y = cp.y + b * cp.y_bstride + (size_t)cp.lo * N + (size_t)tile * CC;
+    u64* dst = P.dst + (size_t)tile * CC;
+    TwF cw[AP];
+    {
+        const TwF* ce = cp.convf + (size_t)pl.dpos[a_idx] * AP;
+#pragma unroll
+        for (int a = 0; a < AP; a++) cw[a] = ce[a];
+    }
+    const double q = P.mc.q, qinv = P.mc.qinv;
+    E v[8];
+    if constexpr (LOG_HI <= 3) {
+        constexpr int KC = 8 / R;
+#pragma unroll
+        for (int rr = 0; rr < R; rr++)
+#pragma unroll
+            for (int kc = 0; kc < KC; kc++) v[rr * KC + kc] = conv_point<AP>(y + ((size_t)rr << 11) + kc * 256 + tid, N, cp.nd, cw, q, qinv);
+        fwd_rows<A, LOG_HI, KC>(v, P.tw, 1, P.mc);
+        A::fwd_round_end(v, P.mc);
+#pragma unroll
+        for (int rr = 0; rr < R; rr++)
+#pragma unroll
+            for (int kc = 0; kc < KC; kc++) dst[((size_t)rr << 11) + kc * 256 + tid] = A::store_mid(v[rr * KC + kc]);
+    } else {
+        __shared__ __attribute__((aligned(16))) E lds[NTT_TILE];
+        constexpr int R8 = R / 8, S2 = LOG_HI - 3, KC2 = 8 / R8;
+        const u32 r0 = tid / CC, col = tid % CC;
+#pragma unroll
+        for (int j = 0; j < 8; j++) v[j] = conv_point<AP>(y + ((size_t)(r0 + R8 * j) << 11) + col, N, cp.nd, cw, q, qinv);
+        fwd_rows<A, 3, 1>(v, P.tw, 1, P.mc);
+        A::fwd_round_end(v, P.mc);
+#pragma unroll
+        for (int j = 0; j < 8; j++) lds[(r0 + R8 * j) * CC + col] = v[j];
+        __syncthreads();
+        const u32 G = tid >> 5, cg = tid & 31;
+#pragma unroll
+        for (int rr = 0; rr < R8; rr++)
+#pragma unroll
+            for (int kc = 0; kc < KC2; kc++) v[rr * KC2 + kc] = lds[(G * R8 + rr) * CC + cg * KC2 + kc];
+        fwd_rows<A, S2, KC2>(v, P.tw, 8 + G, P.mc);
+        A::fwd_round_end(v, P.mc);
+#pragma unroll
+        for (int rr = 0; rr < R8; rr++)
+#pragma unroll
+            for (int kc = 0; kc < KC2; kc++) dst[((size_t)(G * R8 + rr) << 11) + cg * KC2 + kc] = A::store_mid(v[rr * KC2 + kc]);
+    }
+}
+
+// The inverse transform's last store: times 1/N, canonical; or (double-precision arithmetic only) times *scale and centred,
+// as a double: |t| < 0.63 q after the exact product, so the centred representative is t, t - q or t + q.
+template <class A>
+__device__ __forceinline__ u64 inv_last_store(typename A::E v, const typename A::MC& m, const TwF* scale) {
+    if constexpr (std::is_same<A, ArithF64>::value) {
+        if (scale) {
+            const TwF k = *scale;
+            double t = ArithF64::mulmod(v, k.w, k.wq, m.q);
+            const double half = 0.5 * m.q;  // q is odd: no residue sits on the boundary
+            t = t > half ? t - m.q : (t < -half ? t + m.q : t);
+            return (u64)__double_as_longlong(t);
+        }
+    }
+    return A::store_inv_final(v, m);
+}
+
 template <class A, int LOG_HI>
 __global__ __launch_bounds__(NTT_THREADS) void ntt_inv_hi_kernel(NttArgs args, PolyList pl) {
     typedef typename A::E E;
@@ -510,6 +611,7 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_inv_hi_kernel(NttArgs args, P
     const u32 tid = threadIdx.x;
     const PolyRef<A> P = poly_ref<A>(args, pl, blockIdx.y / pl.n, blockIdx.y % pl.n);
     u64* dst = P.dst + (size_t)blockIdx.x * CC;  // the lo pass has already moved the data to dst
+    const TwF* scale = args.inv_scale ? args.inv_scale + pl.dpos[blockIdx.y % pl.n] : nullptr;
     E v[8];
     if constexpr (LOG_HI <= 3) {
         constexpr int KC = 8 / R;
@@ -521,7 +623,7 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_inv_hi_kernel(NttArgs args, P
 #pragma unroll
         for (int rr = 0; rr < R; rr++)
 #pragma unroll
-            for (int kc = 0; kc < KC; kc++) dst[((size_t)rr << 11) + kc * 256 + tid] = A::store_inv_final(v[rr * KC + kc], P.mc);
+            for (int kc = 0; kc < KC; kc++) dst[((size_t)rr << 11) + kc * 256 + tid] = inv_last_store<A>(v[rr * KC + kc], P.mc, scale);
     } else {
         __shared__ __attribute__((aligned(16))) E lds[NTT_TILE];
         constexpr int R8 = R / 8, S2 = LOG_HI - 3, KC2 = 8 / R8;
@@ -541,7 +643,7 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_inv_hi_kernel(NttArgs args, P
         for (int j = 0; j < 8; j++) v[j] = lds[(r0 + R8 * j) * CC + col];
         inv_rows<A, 3, 1>(v, P.tw, 1, P.mc);
 #pragma unroll
-        for (int j = 0; j < 8; j++) dst[((size_t)(r0 + R8 * j) << 11) + col] = A::store_inv_final(v[j], P.mc);
+        for (int j = 0; j < 8; j++) dst[((size_t)(r0 + R8 * j) << 11) + col] = inv_last_store<A>(v[j], P.mc, scale);
     }
 }
 
@@ -605,12 +707,30 @@ static void launch_lo(bool inverse, u32 items, dim3 grid, hipStream_t st, const 
     else launch_lo_it<A, 1>(inverse, grid, st, args, pl);
 }
 
-hipError_t launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, size_t src_bstride, u64* dst,
-                      size_t dst_bstride, const PolyList& pl, u32 batch, hipStream_t st, const u64* const* src_ptrs,
-                      const FwdEpilogue* epilogue) {
+template <int LOG_HI>
+static void launch_hi_conv_ap(u32 ap, dim3 grid, hipStream_t st, const NttArgs& args, const PolyList& pl, const ConvPrologue& cp) {
+    if (ap == 4) hipLaunchKernelGGL((ntt_fwd_hi_conv_kernel<LOG_HI, 4>), grid, dim3(NTT_THREADS), 0, st, args, pl, cp);
+    else if (ap == 8) hipLaunchKernelGGL((ntt_fwd_hi_conv_kernel<LOG_HI, 8>), grid, dim3(NTT_THREADS), 0, st, args, pl, cp);
+    else hipLaunchKernelGGL((ntt_fwd_hi_conv_kernel<LOG_HI, 16>), grid, dim3(NTT_THREADS), 0, st, args, pl, cp);
+}
+static void launch_hi_conv(u32 log_hi, u32 ap, dim3 grid, hipStream_t st, const NttArgs& args, const PolyList& pl, const ConvPrologue& cp) {
+    switch (log_hi) {
+        case 1: launch_hi_conv_ap<1>(ap, grid, st, args, pl, cp); break;
+        case 2: launch_hi_conv_ap<2>(ap, grid, st, args, pl, cp); break;
+        case 3: launch_hi_conv_ap<3>(ap, grid, st, args, pl, cp); break;
+        case 4: launch_hi_conv_ap<4>(ap, grid, st, args, pl, cp); break;
+        case 5: launch_hi_conv_ap<5>(ap, grid, st, args, pl, cp); break;
+        default: launch_hi_conv_ap<6>(ap, grid, st, args, pl, cp); break;
+    }
+}
+
+static hipError_t launch_ntt_any(const ckks_ctx* c, bool inverse, const u64* src, size_t src_bstride, u64* dst,
+                                 size_t dst_bstride, const PolyList& pl, u32 batch, hipStream_t st, const u64* const* src_ptrs,
+                                 const FwdEpilogue* epilogue, const TwF* inv_scale, const ConvPrologue* conv) {
     if (pl.n == 0 || batch == 0) return hipSuccess;
     if (src_ptrs && batch > KS_MAX_BATCH) return hipErrorInvalidValue;
     if (epilogue && (inverse || !ntt_has_epilogue(c) || batch > 2 * KS_MAX_BATCH)) return hipErrorInvalidValue;
+    if ((inv_scale && !inverse) || (conv && inverse) || ((inv_scale || conv) && !ntt_has_modup(c))) return hipErrorInvalidValue;
     const bool f64 = c->ntt_f64;
     NttArgs args;
     args.src = src;
@@ -633,6 +753,7 @@ hipError_t launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, size_t sr
     }
     args.use_src_list = src_ptrs ? 1 : 0;
     for (u32 b = 0; b < KS_MAX_BATCH; b++) args.src_list.p[b] = (src_ptrs && b < batch) ? src_ptrs[b] : nullptr;
+    args.inv_scale = inv_scale;
     const u32 polys = pl.n * batch;
     const dim3 block(NTT_THREADS);
     const double pass_bytes = 16.0 * polys * c->N;
@@ -662,7 +783,13 @@ hipError_t launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, size_t sr
     if (!inverse) {
         if (c->log_hi > 0) {
             args.last = 0;
-            { ProfScope ps__(c, K_NTT_FWD_HI, st, pass_bytes, hi_ops); hi(args, pl); }
+            if (conv) {  // reads the digit's nd limbs for every target limb (from cache after the first), writes the target limbs
+                ProfScope ps__(c, K_NTT_FWD_HI, st, 8.0 * c->N * batch * ((double)conv->nd + pl.n), hi_ops);
+                launch_hi_conv(c->log_hi, c->alpha_pad, grid, st, args, pl, *conv);
+            } else {
+                ProfScope ps__(c, K_NTT_FWD_HI, st, pass_bytes, hi_ops);
+                hi(args, pl);
+            }
             if (epilogue) {  // reads w and v, writes the quotients (plus the addends it reads)
                 ProfScope ps__(c, K_NTT_FWD_LO, st, 1.5 * pass_bytes, lo_ops);
                 if (f64) launch_lo_div<ArithF64>(lo_items, grid_lo, st, second, pd, *epilogue);
@@ -681,4 +808,21 @@ hipError_t launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, size_t sr
         if (c->log_hi > 0) { ProfScope ps__(c, K_NTT_INV_HI, st, pass_bytes, hi_ops); hi(second, pd); }
     }
     return hipGetLastError();
+}
+
+hipError_t launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, size_t src_bstride, u64* dst, size_t dst_bstride,
+                      const PolyList& pl, u32 batch, hipStream_t st, const u64* const* src_ptrs, const FwdEpilogue* epilogue,
+                      const TwF* inv_scale) {
+    return launch_ntt_any(c, inverse, src, src_bstride, dst, dst_bstride, pl, batch, st, src_ptrs, epilogue, inv_scale, nullptr);
+}
+
+hipError_t launch_ntt_modup(const ckks_ctx* c, u32 level, u32 j, const double* y, size_t y_bstride, u64* dst, size_t dst_bstride,
+                            const PolyList& pl, u32 batch, hipStream_t st) {
+    ConvPrologue cp;
+    cp.y = y;
+    cp.y_bstride = y_bstride;
+    cp.convf = c->modup_table_f(level, j);
+    cp.lo = c->digit_lo(j);
+    cp.nd = c->digit_hi(j, level) - cp.lo;
+    return launch_ntt_any(c, false, dst, dst_bstride, dst, dst_bstride, pl, batch, st, nullptr, nullptr, nullptr, &cp);
 }
