@@ -118,7 +118,7 @@ int run_modup(const ckks_ctx* c, u32 level, const u64* const* srcs, u32 n, const
     // of the extended digit).
     const bool fused = ntt_has_modup(c);
     HIP_TRY(launch_ntt(c, true, nullptr, 0, ws.y, L1, range_list(0, L1, 0), n, st, srcs, nullptr,
-                       fused ? c->d_modup_prep_f + (size_t)level * c->num_q : nullptr));
+                       fused ? c->d_modup_prep_f + (size_t)level * c->num_q : nullptr));  // (positions 0..level are moduli 0..level)
     const PtrList8 cl = ptr_list(srcs, n);
     for (u32 j = 0; j < beta; j++) {
         const u32 lo = c->digit_lo(j), hi = c->digit_hi(j, level);
@@ -166,6 +166,12 @@ int run_moddown(const ckks_ctx* c, u32 level, const KsWs& ws, u32 n, const Final
         PolyList dl = range_list(level, k + 1, c->num_q - 1);  // positions level.. ; moduli fixed up below
         dl.mod[0] = (unsigned char)level;
         for (u32 a = 1; a <= k; a++) dl.mod[a] = (unsigned char)(c->num_q + a - 1);
+        if (ntt_has_modup(c)) {  // conversion inside the forward transform's first pass, last step inside its second
+            HIP_TRY(launch_ntt(c, true, ws.v, E, ws.v, E, dl, 2 * n, st, nullptr, nullptr, c->d_moddown_rs_prep_f + (size_t)level * c->M));
+            const FwdEpilogue ep = moddown_epilogue(c, level, true, ws.v, items, n);
+            HIP_TRY(launch_ntt_moddown(c, level, true, (const double*)ws.v, ws.w, 2 * n, st, &ep));
+            return CKKS_OK;
+        }
         HIP_TRY(launch_ntt(c, true, ws.v, E, ws.v, E, dl, 2 * n, st));
         HIP_TRY(launch_moddown_conv(c, level, true, ws.v, ws.w, 2 * n, st));
         if (ntt_has_epilogue(c)) {  // the last step rides on the transform's stores
@@ -175,6 +181,12 @@ int run_moddown(const ckks_ctx* c, u32 level, const KsWs& ws, u32 n, const Final
         }
         HIP_TRY(launch_ntt(c, false, ws.w, level, ws.w, level, range_list(0, level, 0), 2 * n, st));
         HIP_TRY(launch_moddown_final(c, level, true, ws.v, ws.w, items, n, st));
+        return CKKS_OK;
+    }
+    if (ntt_has_modup(c)) {
+        HIP_TRY(launch_ntt(c, true, ws.v, E, ws.v, E, range_list(L1, k, c->num_q), 2 * n, st, nullptr, nullptr, c->d_moddown_prep_f));
+        const FwdEpilogue ep = moddown_epilogue(c, level, false, ws.v, items, n);
+        HIP_TRY(launch_ntt_moddown(c, level, false, (const double*)ws.v, ws.w, 2 * n, st, &ep));
         return CKKS_OK;
     }
     HIP_TRY(launch_ntt(c, true, ws.v, E, ws.v, E, range_list(L1, k, c->num_q), 2 * n, st));  // P-part -> coefficients

@@ -73,6 +73,8 @@ extern "C" void ckks_ctx_destroy(ckks_ctx* c) {
     (void)hipFree(c->d_modup_prep_f);
     (void)hipFree(c->d_moddown_f);
     (void)hipFree(c->d_moddown_rs_f);
+    (void)hipFree(c->d_moddown_prep_f);
+    (void)hipFree(c->d_moddown_rs_prep_f);
     (void)hipFree(c->d_rescale);
     if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
     if (c->ev_join) (void)hipEventDestroy(c->ev_join);
@@ -274,7 +276,7 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
         }
     }
     // the conversion constants as doubles (value, value / target modulus) for the double-precision conversions
-    std::vector<TwF> modup_f, modup_prep_f, moddown_f, moddown_rs_f;
+    std::vector<TwF> modup_f, modup_prep_f, moddown_f, moddown_rs_f, moddown_prep_f, moddown_rs_prep_f;
     if (c->dnum && c->ntt_f64) {
         const u32 nq = c->num_q;
         modup_f.assign((size_t)nq * c->dnum * M * c->alpha_pad, TwF{0.0, 0.0});
@@ -306,6 +308,20 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
                 const double w = (double)moddown[2 * c->k_pad + (size_t)i * c->k_pad + a];
                 moddown_f[(size_t)i * c->k_pad + a] = TwF{w, w / (double)c->mod[i]};
             }
+        // what the inverse transform in front of ModDown scales a dropped limb by: 1/N times the limb's conversion constant
+        auto prep = [&](u64 inv, u32 m) {
+            const u64 q = c->mod[m];
+            const double w = (double)h_mulmod(inv, c->mc[m].n_inv, q);
+            return TwF{w, w / (double)q};
+        };
+        moddown_prep_f.assign(M, TwF{0.0, 0.0});
+        for (u32 a = 0; a < c->num_p; a++) moddown_prep_f[nq + a] = prep(moddown[a], nq + a);
+        moddown_rs_prep_f.assign((size_t)nq * M, TwF{0.0, 0.0});
+        for (u32 l = 1; l < nq; l++) {
+            const u64* tab = moddown_rs.data() + l * c->moddown_rs_stride();
+            moddown_rs_prep_f[(size_t)l * M + l] = prep(tab[0], l);
+            for (u32 a = 0; a < c->num_p; a++) moddown_rs_prep_f[(size_t)l * M + nq + a] = prep(tab[1 + a], nq + a);
+        }
         moddown_rs_f.assign((size_t)nq * nq * c->k2_pad, TwF{0.0, 0.0});
         for (u32 l = 1; l < nq; l++) {
             const u64* tab = moddown_rs.data() + l * c->moddown_rs_stride();
@@ -341,6 +357,8 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
     if (e == hipSuccess) e = upload(modup_prep_f, &c->d_modup_prep_f);
     if (e == hipSuccess) e = upload(moddown_f, &c->d_moddown_f);
     if (e == hipSuccess) e = upload(moddown_rs_f, &c->d_moddown_rs_f);
+    if (e == hipSuccess) e = upload(moddown_prep_f, &c->d_moddown_prep_f);
+    if (e == hipSuccess) e = upload(moddown_rs_prep_f, &c->d_moddown_rs_prep_f);
     if (e == hipSuccess) e = upload(resc, &c->d_rescale);
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {

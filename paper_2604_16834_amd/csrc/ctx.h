@@ -139,6 +139,8 @@ struct ckks_ctx {
     TwF* d_modup_prep_f = nullptr;    // [level][num_q]: N^-1 (Q_j/q_i)^-1 mod q_i, what the inverse transform in front of ModUp scales by
     TwF* d_moddown_f = nullptr;       // [num_q][k_pad]
     TwF* d_moddown_rs_f = nullptr;    // [level][num_q][k2_pad]
+    TwF* d_moddown_prep_f = nullptr;     // [M], by modulus: N^-1 (P/p_a)^-1 mod p_a at the special primes (zero elsewhere)
+    TwF* d_moddown_rs_prep_f = nullptr;  // [level][M], by modulus: N^-1 (P q_l / m)^-1 mod m for m in {q_l, p_0..p_{k-1}}
     const TwF* modup_table_f(u32 level, u32 j) const { return d_modup_f + ((size_t)level * dnum + j) * M * alpha_pad; }
     const TwF* moddown_rs_table_f(u32 level) const { return d_moddown_rs_f + (size_t)level * num_q * k2_pad; }
 
@@ -201,10 +203,15 @@ hipError_t launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, size_t sr
                       size_t dst_bstride, const PolyList& pl, u32 batch, hipStream_t st, const u64* const* src_ptrs = nullptr,
                       const FwdEpilogue* epilogue = nullptr, const TwF* inv_scale = nullptr);
 // ModUp fused into transforms (contexts with ntt_f64 and the two-pass transform): the inverse transform of the polynomial
-// scales limb i by inv_scale[i] instead of 1/N and stores the CENTRED residue as a double (launch_ntt with inv_scale);
+// scales the limb with modulus index m by inv_scale[m] instead of 1/N and stores the CENTRED residue as a double (launch_ntt with inv_scale);
 // launch_ntt_modup then evaluates the basis conversion of digit j, y [batch][level+1][N] doubles -> the pl.n target limbs
 // pl.dpos[] of dst (batch stride dst_bstride limb-polys), inside the first pass of their forward transforms.
 inline bool ntt_has_modup(const ckks_ctx* c) { return c->ntt_f64 && c->log_n > CKKS_TILE_LOG && c->d_modup_prep_f != nullptr; }
+// The same for ModDown's conversion: y are the 2*batch extended polynomials ([E][N] each, the dropped limbs left as scaled
+// centred doubles by launch_ntt with the moddown prep table), dst the converted dropped part ([n_out][N] per polynomial,
+// NTT form), epilogue what the second pass does with it.  merged: the dropped set is {q_level, p_0..p_{k-1}}.
+hipError_t launch_ntt_moddown(const ckks_ctx* c, u32 level, bool merged, const double* y, u64* dst, u32 batch, hipStream_t st,
+                              const FwdEpilogue* epilogue);
 hipError_t launch_ntt_modup(const ckks_ctx* c, u32 level, u32 j, const double* y, size_t y_bstride, u64* dst, size_t dst_bstride,
                             const PolyList& pl, u32 batch, hipStream_t st);
 // whether launch_ntt can apply an epilogue in this ring (it needs the two-pass transform)

@@ -198,7 +198,7 @@ struct NttArgs {
     u32 lo_group;        // slices per group of the lo-pass numbering (0: plain)
     u32 use_src_list;    // batch item b reads src_list.p[b] instead of src + b*src_bstride*N
     PtrList8 src_list;
-    const TwF* inv_scale;  // inverse, last pass (double-precision arithmetic): limb at position p is scaled by inv_scale[p]
+    const TwF* inv_scale;  // inverse, last pass (double-precision arithmetic): the limb of modulus m is scaled by inv_scale[m]
                            // instead of 1/N and stored as the centred residue in a double (the form ModUp's conversion reads)
 };
 
@@ -507,23 +507,29 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_hi_kernel(NttArgs args, P
     }
 }
 
-// The forward hi pass with ModUp's basis conversion in front of it: the points of target limb e (position pl.dpos[a]) are
-//   sum_i yhat_i * [Q_j/q_i]_{q_e}  mod q_e
-// evaluated from the digit's centred residues yhat (doubles, [batch][level+1][N]) as the tile is loaded: the converted
-// polynomial is never written in coefficient form.  convf: [E][AP] (constant, constant / q_e); lo, nd: the digit's limbs.
+// The forward hi pass with a basis conversion (ModUp's or ModDown's) in front of it: the points of the target limb at
+// position e = pl.dpos[a] are
+//   sum_i yhat_i * [B/b_i]_{q_e}  mod q_e
+// evaluated from the source basis' centred residues yhat (doubles, nd limbs from position lo of each batch item of y)
+// as the tile is loaded: the converted polynomial is never written in coefficient form.
+// convf: [position][ap] (constant, constant / q_e), rows padded with zeros to ap = 4, 8, 12 or 16 entries.
 struct ConvPrologue {
     const double* y;
     size_t y_bstride;  // elements
     const TwF* convf;
     u32 lo, nd;
+    u32 ap, pad;
 };
 
+// the source residues of one point: no branch around the loads (entries beyond the nd source limbs re-read the last
+// one against a zero constant)
 template <int AP>
-__device__ __forceinline__ double conv_point(const double* __restrict__ yp, size_t N, u32 nd, const TwF* cw, double q, double qinv) {
-    // no branch around the loads: entries beyond the digit's nd limbs re-read its last limb against a zero constant
-    double yv[AP];
+__device__ __forceinline__ void conv_load(double (&yv)[AP], const double* __restrict__ yp, size_t N, u32 nd) {
 #pragma unroll
     for (int a = 0; a < AP; a++) yv[a] = yp[(size_t)((u32)a < nd ? a : nd - 1) * N];
+}
+template <int AP>
+__device__ __forceinline__ double conv_sum(const double (&yv)[AP], const TwF* cw, double q, double qinv) {
     double s = 0.0;
 #pragma unroll
     for (int a = 0; a < AP; a++) {
@@ -533,58 +539,83 @@ __device__ __forceinline__ double conv_point(const double* __restrict__ yp, size
     return __builtin_fma(-ArithF64::round_mul(s, qinv), q, s);
 }
 
-template <int LOG_HI, int AP>
+// One workgroup converts and transforms the same tile of T target limbs: the source residues are fetched once for all T
+// (the fetch, from L2 after the first, is what bounds a one-target-per-workgroup version).
+template <int LOG_HI, int AP, int T>
 __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_hi_conv_kernel(NttArgs args, PolyList pl, ConvPrologue cp) {
     typedef ArithF64 A;
     typedef double E;
     constexpr int R = 1 << LOG_HI, CC = NTT_TILE / R;
-    const u32 tid = threadIdx.x, tile = blockIdx.x, b = blockIdx.y / pl.n, a_idx = blockIdx.y % pl.n;
-    const PolyRef<A> P = poly_ref<A>(args, pl, b, a_idx);
+    const u32 groups = (pl.n + T - 1) / T;
+    const u32 tid = threadIdx.x, tile = blockIdx.x, b = blockIdx.y / groups, a0 = (blockIdx.y % groups) * T;
     const size_t N = (size_t)1 << args.log_n;
     const double* y = cp.y + b * cp.y_bstride + (size_t)cp.lo * N + (size_t)tile * CC;
-    u64* dst = P.dst + (size_t)tile * CC;
-    TwF cw[AP];
-    {
+    PolyRef<A> P[T];
+    TwF cw[T][AP];
+#pragma unroll
+    for (int t = 0; t < T; t++) {
+        const u32 a_idx = a0 + t < pl.n ? a0 + t : pl.n - 1;  // a ragged last group repeats its last limb and skips the store
+        P[t] = poly_ref<A>(args, pl, b, a_idx);
         const TwF* ce = cp.convf + (size_t)pl.dpos[a_idx] * AP;
 #pragma unroll
-        for (int a = 0; a < AP; a++) cw[a] = ce[a];
+        for (int a = 0; a < AP; a++) cw[t][a] = ce[a];
     }
-    const double q = P.mc.q, qinv = P.mc.qinv;
-    E v[8];
+    E v[T][8];
     if constexpr (LOG_HI <= 3) {
         constexpr int KC = 8 / R;
 #pragma unroll
         for (int rr = 0; rr < R; rr++)
 #pragma unroll
-            for (int kc = 0; kc < KC; kc++) v[rr * KC + kc] = conv_point<AP>(y + ((size_t)rr << 11) + kc * 256 + tid, N, cp.nd, cw, q, qinv);
-        fwd_rows<A, LOG_HI, KC>(v, P.tw, 1, P.mc);
-        A::fwd_round_end(v, P.mc);
+            for (int kc = 0; kc < KC; kc++) {
+                double yv[AP];
+                conv_load<AP>(yv, y + ((size_t)rr << 11) + kc * 256 + tid, N, cp.nd);
 #pragma unroll
-        for (int rr = 0; rr < R; rr++)
+                for (int t = 0; t < T; t++) v[t][rr * KC + kc] = conv_sum<AP>(yv, cw[t], P[t].mc.q, P[t].mc.qinv);
+            }
 #pragma unroll
-            for (int kc = 0; kc < KC; kc++) dst[((size_t)rr << 11) + kc * 256 + tid] = A::store_mid(v[rr * KC + kc]);
+        for (int t = 0; t < T; t++) {
+            if (a0 + t >= pl.n) break;
+            u64* dst = P[t].dst + (size_t)tile * CC;
+            fwd_rows<A, LOG_HI, KC>(v[t], P[t].tw, 1, P[t].mc);
+            A::fwd_round_end(v[t], P[t].mc);
+#pragma unroll
+            for (int rr = 0; rr < R; rr++)
+#pragma unroll
+                for (int kc = 0; kc < KC; kc++) dst[((size_t)rr << 11) + kc * 256 + tid] = A::store_mid(v[t][rr * KC + kc]);
+        }
     } else {
         __shared__ __attribute__((aligned(16))) E lds[NTT_TILE];
         constexpr int R8 = R / 8, S2 = LOG_HI - 3, KC2 = 8 / R8;
         const u32 r0 = tid / CC, col = tid % CC;
 #pragma unroll
-        for (int j = 0; j < 8; j++) v[j] = conv_point<AP>(y + ((size_t)(r0 + R8 * j) << 11) + col, N, cp.nd, cw, q, qinv);
-        fwd_rows<A, 3, 1>(v, P.tw, 1, P.mc);
-        A::fwd_round_end(v, P.mc);
+        for (int j = 0; j < 8; j++) {
+            double yv[AP];
+            conv_load<AP>(yv, y + ((size_t)(r0 + R8 * j) << 11) + col, N, cp.nd);
 #pragma unroll
-        for (int j = 0; j < 8; j++) lds[(r0 + R8 * j) * CC + col] = v[j];
-        __syncthreads();
+            for (int t = 0; t < T; t++) v[t][j] = conv_sum<AP>(yv, cw[t], P[t].mc.q, P[t].mc.qinv);
+        }
         const u32 G = tid >> 5, cg = tid & 31;
 #pragma unroll
-        for (int rr = 0; rr < R8; rr++)
+        for (int t = 0; t < T; t++) {
+            if (a0 + t >= pl.n) break;  // uniform over the workgroup
+            u64* dst = P[t].dst + (size_t)tile * CC;
+            if (t) __syncthreads();  // the previous limb's exchange has been read
+            fwd_rows<A, 3, 1>(v[t], P[t].tw, 1, P[t].mc);
+            A::fwd_round_end(v[t], P[t].mc);
 #pragma unroll
-            for (int kc = 0; kc < KC2; kc++) v[rr * KC2 + kc] = lds[(G * R8 + rr) * CC + cg * KC2 + kc];
-        fwd_rows<A, S2, KC2>(v, P.tw, 8 + G, P.mc);
-        A::fwd_round_end(v, P.mc);
+            for (int j = 0; j < 8; j++) lds[(r0 + R8 * j) * CC + col] = v[t][j];
+            __syncthreads();
 #pragma unroll
-        for (int rr = 0; rr < R8; rr++)
+            for (int rr = 0; rr < R8; rr++)
 #pragma unroll
-            for (int kc = 0; kc < KC2; kc++) dst[((size_t)(G * R8 + rr) << 11) + cg * KC2 + kc] = A::store_mid(v[rr * KC2 + kc]);
+                for (int kc = 0; kc < KC2; kc++) v[t][rr * KC2 + kc] = lds[(G * R8 + rr) * CC + cg * KC2 + kc];
+            fwd_rows<A, S2, KC2>(v[t], P[t].tw, 8 + G, P[t].mc);
+            A::fwd_round_end(v[t], P[t].mc);
+#pragma unroll
+            for (int rr = 0; rr < R8; rr++)
+#pragma unroll
+                for (int kc = 0; kc < KC2; kc++) dst[((size_t)(G * R8 + rr) << 11) + cg * KC2 + kc] = A::store_mid(v[t][rr * KC2 + kc]);
+        }
     }
 }
 
@@ -611,7 +642,7 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_inv_hi_kernel(NttArgs args, P
     const u32 tid = threadIdx.x;
     const PolyRef<A> P = poly_ref<A>(args, pl, blockIdx.y / pl.n, blockIdx.y % pl.n);
     u64* dst = P.dst + (size_t)blockIdx.x * CC;  // the lo pass has already moved the data to dst
-    const TwF* scale = args.inv_scale ? args.inv_scale + pl.dpos[blockIdx.y % pl.n] : nullptr;
+    const TwF* scale = args.inv_scale ? args.inv_scale + pl.mod[blockIdx.y % pl.n] : nullptr;
     E v[8];
     if constexpr (LOG_HI <= 3) {
         constexpr int KC = 8 / R;
@@ -707,11 +738,14 @@ static void launch_lo(bool inverse, u32 items, dim3 grid, hipStream_t st, const 
     else launch_lo_it<A, 1>(inverse, grid, st, args, pl);
 }
 
+constexpr u32 CONV_TARGETS = 4;  // target limbs per workgroup of the converting hi pass
 template <int LOG_HI>
 static void launch_hi_conv_ap(u32 ap, dim3 grid, hipStream_t st, const NttArgs& args, const PolyList& pl, const ConvPrologue& cp) {
-    if (ap == 4) hipLaunchKernelGGL((ntt_fwd_hi_conv_kernel<LOG_HI, 4>), grid, dim3(NTT_THREADS), 0, st, args, pl, cp);
-    else if (ap == 8) hipLaunchKernelGGL((ntt_fwd_hi_conv_kernel<LOG_HI, 8>), grid, dim3(NTT_THREADS), 0, st, args, pl, cp);
-    else hipLaunchKernelGGL((ntt_fwd_hi_conv_kernel<LOG_HI, 16>), grid, dim3(NTT_THREADS), 0, st, args, pl, cp);
+    constexpr int T = CONV_TARGETS;
+    if (ap == 4) hipLaunchKernelGGL((ntt_fwd_hi_conv_kernel<LOG_HI, 4, T>), grid, dim3(NTT_THREADS), 0, st, args, pl, cp);
+    else if (ap == 8) hipLaunchKernelGGL((ntt_fwd_hi_conv_kernel<LOG_HI, 8, T>), grid, dim3(NTT_THREADS), 0, st, args, pl, cp);
+    else if (ap == 12) hipLaunchKernelGGL((ntt_fwd_hi_conv_kernel<LOG_HI, 12, T>), grid, dim3(NTT_THREADS), 0, st, args, pl, cp);
+    else hipLaunchKernelGGL((ntt_fwd_hi_conv_kernel<LOG_HI, 16, T>), grid, dim3(NTT_THREADS), 0, st, args, pl, cp);
 }
 static void launch_hi_conv(u32 log_hi, u32 ap, dim3 grid, hipStream_t st, const NttArgs& args, const PolyList& pl, const ConvPrologue& cp) {
     switch (log_hi) {
@@ -731,6 +765,8 @@ static hipError_t launch_ntt_any(const ckks_ctx* c, bool inverse, const u64* src
     if (src_ptrs && batch > KS_MAX_BATCH) return hipErrorInvalidValue;
     if (epilogue && (inverse || !ntt_has_epilogue(c) || batch > 2 * KS_MAX_BATCH)) return hipErrorInvalidValue;
     if ((inv_scale && !inverse) || (conv && inverse) || ((inv_scale || conv) && !ntt_has_modup(c))) return hipErrorInvalidValue;
+    if (conv && (conv->nd == 0 || conv->nd > conv->ap || (conv->ap != 4 && conv->ap != 8 && conv->ap != 12 && conv->ap != 16)))
+        return hipErrorInvalidValue;
     const bool f64 = c->ntt_f64;
     NttArgs args;
     args.src = src;
@@ -785,7 +821,7 @@ static hipError_t launch_ntt_any(const ckks_ctx* c, bool inverse, const u64* src
             args.last = 0;
             if (conv) {  // reads the digit's nd limbs for every target limb (from cache after the first), writes the target limbs
                 ProfScope ps__(c, K_NTT_FWD_HI, st, 8.0 * c->N * batch * ((double)conv->nd + pl.n), hi_ops);
-                launch_hi_conv(c->log_hi, c->alpha_pad, grid, st, args, pl, *conv);
+                launch_hi_conv(c->log_hi, conv->ap, dim3(grid.x, (pl.n + CONV_TARGETS - 1) / CONV_TARGETS * batch), st, args, pl, *conv);
             } else {
                 ProfScope ps__(c, K_NTT_FWD_HI, st, pass_bytes, hi_ops);
                 hi(args, pl);
@@ -824,5 +860,25 @@ hipError_t launch_ntt_modup(const ckks_ctx* c, u32 level, u32 j, const double* y
     cp.convf = c->modup_table_f(level, j);
     cp.lo = c->digit_lo(j);
     cp.nd = c->digit_hi(j, level) - cp.lo;
+    cp.ap = c->alpha_pad;
+    cp.pad = 0;
     return launch_ntt_any(c, false, dst, dst_bstride, dst, dst_bstride, pl, batch, st, nullptr, nullptr, nullptr, &cp);
+}
+
+hipError_t launch_ntt_moddown(const ckks_ctx* c, u32 level, bool merged, const double* y, u64* dst, u32 batch, hipStream_t st,
+                              const FwdEpilogue* epilogue) {
+    if (merged && level == 0) return hipErrorInvalidValue;
+    const u32 n_out = merged ? level : level + 1;
+    ConvPrologue cp;
+    cp.y = y;
+    cp.y_bstride = (size_t)c->ext_limbs(level) * c->N;
+    cp.convf = merged ? c->moddown_rs_table_f(level) : c->d_moddown_f;
+    cp.lo = merged ? level : level + 1;  // the dropped limbs sit at consecutive positions of the extended polynomial
+    cp.nd = merged ? c->num_p + 1 : c->num_p;
+    cp.ap = merged ? c->k2_pad : c->k_pad;
+    cp.pad = 0;
+    PolyList pl;
+    for (u32 a = 0; a < CKKS_MAX_MODULI; a++) pl.spos[a] = pl.dpos[a] = pl.mod[a] = (unsigned char)(a < n_out ? a : 0);
+    pl.n = n_out;
+    return launch_ntt_any(c, false, dst, n_out, dst, n_out, pl, batch, st, nullptr, epilogue, nullptr, &cp);
 }
