@@ -680,3 +680,31 @@ def test_error_codes(ks_setup):
     with pytest.raises(hx.CkksError) as e:
         hx.ckks_ntt_fwd(ctx, hx.empty(1, 1, orc.N), [99])
     assert e.value.code == hx.binding.CKKS_ERR_INVALID_ARG
+
+
+def test_empty_inputs_are_rejected(ks_setup):
+    """A zero count is an argument error at every entry point (nothing is enqueued)."""
+    p, orc, ctx, s, s_ntt, rlk, d_rlk = ks_setup
+    level = 2
+    ct = hx.from_host(rand_ct(np.random.default_rng(2), p.moduli, level, orc.N))
+    pt = hx.from_host(rand_poly(np.random.default_rng(3), p.moduli[:level + 1], orc.N))
+    bad = hx.binding.CKKS_ERR_INVALID_ARG
+    with pytest.raises(hx.CkksError) as e:
+        hx.ckks_rotate_hoisted(ctx, ct, level, [], [])
+    assert e.value.code == bad
+    with pytest.raises(hx.CkksError) as e:
+        hx.ckks_ptct_mac(ctx, [], [], level)
+    assert e.value.code == bad
+    with pytest.raises(hx.CkksError) as e:
+        hx.ckks_ntt_fwd(ctx, hx.empty(1, 1, orc.N)[:0], [], batch=0)
+    assert e.value.code == bad
+    with pytest.raises(hx.CkksError) as e:
+        hx.ckks_ntt_inv(ctx, hx.empty(1, 1, orc.N)[:0], [0], batch=0)
+    assert e.value.code == bad
+    with pytest.raises(hx.CkksError) as e:
+        hx.he_conv_batched(ctx, 8, 8, 0, level, [ct], [None] * 9, hx.empty(9, level + 1, orc.N), hx.empty(1, 1, 9, level + 1), 1)
+    assert e.value.code == bad
+    # the operands above are still usable afterwards: one term, accumulate off
+    acc = hx.ckks_ptct_mac(ctx, [pt], [ct], level)
+    assert np.array_equal(hx.to_host(acc), orc.ptct_mac([hx.to_host(pt)], [hx.to_host(ct)], level))
+
