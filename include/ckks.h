@@ -142,7 +142,10 @@ int ckks_keyswitch(const ckks_ctx* ctx, const uint64_t* d_c, uint32_t level, con
  * hoisted = 1: c1 is decomposed and extended once and every rotation permutes the extended digits
  * ("fast rotations"); hoisted = 0: each rotation permutes the ciphertext and key-switches the
  * permuted c1.  Both orders give the same residues (centred digits commute with the automorphism).
- * h_d_outs: host array of n_rot device pointers, each uint64[2][level+1][N]. */
+ * h_d_outs: host array of n_rot device pointers, each uint64[2][level+1][N].
+ * Workspace: ckks_workspace_bytes(ctx, CKKS_OP_ROTATE, level, n_rot) lets up to 8 rotations share every launch
+ * but the inner products; a smaller one is accepted down to the size for n_rot = 1 (unhoisted rotations then go
+ * in smaller batches, same residues), below that CKKS_ERR_WORKSPACE_TOO_SMALL. */
 int ckks_rotate_hoisted(const ckks_ctx* ctx, const uint64_t* d_ct, uint32_t level,
                         const int32_t* h_offsets, uint32_t n_rot, const ckks_key* const* keys,
                         uint64_t* const* h_d_outs, int hoisted, void* d_ws, size_t ws_bytes, void* stream);

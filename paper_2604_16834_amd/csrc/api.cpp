@@ -705,10 +705,15 @@ size_t ckks_workspace_bytes(const ckks_ctx* c, int op, uint32_t level, uint32_t 
     const u32 nb = count < 1 ? 1 : (count > CT_BATCH ? CT_BATCH : count);
     switch (op) {
         case CKKS_OP_KEYSWITCH: return c->dnum ? ws_ks(c, level, 1, 1) : 0;
-        case CKKS_OP_ROTATE:  // more than one batch: a second set of inner-product and conversion buffers (two batches in flight)
-            return c->dnum ? ws_ks(c, level, 1, nb) + blk(L1 * N) +
-                                 (count > CT_BATCH && c->side ? blk((size_t)nb * 2 * c->ext_limbs(level) * N) + blk((size_t)nb * 2 * L1 * N) : 0)
-                           : 0;
+        case CKKS_OP_ROTATE: {
+            if (!c->dnum) return 0;
+            // hoisted, more than one batch: a second set of inner-product and conversion buffers (two batches in flight);
+            // unhoisted: every rotation of a batch has its own permuted copy and its own digits
+            const size_t hoisted = ws_ks(c, level, 1, nb) + blk(L1 * N) +
+                                   (count > CT_BATCH && c->side ? blk((size_t)nb * 2 * c->ext_limbs(level) * N) + blk((size_t)nb * 2 * L1 * N) : 0);
+            const size_t unhoisted = ws_ks(c, level, nb, nb) + blk((size_t)nb * L1 * N);
+            return hoisted > unhoisted ? hoisted : unhoisted;
+        }
         case CKKS_OP_RESCALE: return level >= 1 ? ws_rescale(c, level, 1) : 0;
         case CKKS_OP_CTCT_MUL_RELIN: return c->dnum ? ws_ctct(c, level, 1) : 0;
         // more than one batch of channels: two batches in flight (one on the library's side stream), each with its own scratch
@@ -856,16 +861,26 @@ int ckks_rotate_hoisted(const ckks_ctx* c, const uint64_t* d_ct, uint32_t level,
         if (!keys || !keys[t]) return set_err(c, CKKS_ERR_NO_KEY, "rotation key missing");
         if (keys[t]->galois_elt != g) return set_err(c, CKKS_ERR_NO_KEY, "rotation key was made for another offset");
     }
-    // hoisted rotations go through the ModDown kernels in batches of up to CT_BATCH
-    const u32 rb = hoisted ? (n_keyed < CT_BATCH ? (n_keyed ? n_keyed : 1) : CT_BATCH) : 1;
+    // rotations go through the kernels in batches of up to CT_BATCH: hoisted ones share the digits and batch their ModDown;
+    // unhoisted ones each have their own permuted polynomial and digits and batch everything but the inner product (one key
+    // each), in batches as large as the workspace holds (one at a time in the smallest workspace that is accepted)
+    u32 rb = n_keyed < CT_BATCH ? (n_keyed ? n_keyed : 1) : CT_BATCH;
     Arena ar(d_ws, ws_bytes);
     KsWs ws = {};
     u64* pc1 = nullptr;
     if (n_keyed) {
-        if (!carve_ks(c, level, 1, rb, ar, ws)) return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for rotation");
-        if (!hoisted) {
-            pc1 = ar.take(L1 * N);
-            if (!ar.ok()) return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for rotation");
+        if (hoisted) {
+            if (!carve_ks(c, level, 1, rb, ar, ws)) return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for rotation");
+        } else {
+            for (;; rb--) {
+                Arena probe(d_ws, ws_bytes);
+                KsWs w;
+                const bool fits = carve_ks(c, level, rb, rb, probe, w) && (probe.take((size_t)rb * L1 * N), probe.ok());
+                if (fits) break;
+                if (rb == 1) return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for rotation");
+            }
+            carve_ks(c, level, rb, rb, ar, ws);
+            pc1 = ar.take((size_t)rb * L1 * N);
         }
     }
     hipStream_t st = (hipStream_t)stream;
@@ -898,7 +913,24 @@ int ckks_rotate_hoisted(const ckks_ctx* c, const uint64_t* d_ct, uint32_t level,
         return (e != hipSuccess && rc == CKKS_OK) ? set_hip_err(c, e) : rc;
     };
     FinalItem items[CT_BATCH];
+    const ckks_key* pend_key[CT_BATCH];
     u32 nb = 0, lane = 0;
+    // the pending unhoisted rotations: sigma_g(c1) of each, one decomposition and one ModDown for the batch
+    auto flush_unhoisted = [&]() -> int {
+        const u64* srcs[CT_BATCH];
+        for (u32 b = 0; b < nb; b++) {
+            u64* dst = pc1 + (size_t)b * L1 * N;
+            HIP_TRY(launch_automorph(c, (u32)L1, c1, items[b].g, dst, st));
+            srcs[b] = dst;
+        }
+        int rc = run_modup(c, level, srcs, nb, ws, st);
+        if (rc) return rc;
+        // the digits already belong to sigma_g(c1): no gather in the inner product, only on c0
+        for (u32 b = 0; b < nb; b++) HIP_TRY(launch_key_inner(c, level, dsrc(c, ws, b), pend_key[b]->d_key, 1, ws.v + b * ws.v_b, st));
+        rc = run_moddown(c, level, ws, nb, items, st);
+        nb = 0;
+        return rc;
+    };
     for (u32 t = 0; t < n_rot; t++) {
         const u32 g = ckks_galois_element(c, h_offsets[t]);
         u64* out = (u64*)h_d_outs[t];
@@ -920,17 +952,15 @@ int ckks_rotate_hoisted(const ckks_ctx* c, const uint64_t* d_ct, uint32_t level,
                 if (two_lanes) lane ^= 1;
             }
         } else {
-            HIP_TRY(launch_automorph(c, (u32)L1, c1, g, pc1, st));
-            const u64* src = pc1;
-            int rc = run_modup(c, level, &src, 1, ws, st);
-            if (rc) return rc;
-            // the digits already belong to sigma_g(c1): no gather in the inner product, only on c0
-            HIP_TRY(launch_key_inner(c, level, dsrc(c, ws, 0), keys[t]->d_key, 1, ws.v, st));
-            const FinalItem item = {c0, nullptr, nullptr, out, g, 0};
-            if ((rc = run_moddown(c, level, ws, 1, &item, st))) return rc;
+            items[nb] = FinalItem{c0, nullptr, nullptr, out, g, 0};
+            pend_key[nb] = keys[t];
+            if (++nb == rb)
+                if (int rc = flush_unhoisted()) return rc;
         }
     }
-    if (nb) {
+    if (nb && !hoisted) {
+        if (int rc = flush_unhoisted()) return rc;
+    } else if (nb) {
         int rc = run_moddown(c, level, lane_ws[lane], nb, items, lane ? c->side : st);
         if (rc) return join(rc);
     }

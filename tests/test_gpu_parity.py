@@ -88,6 +88,29 @@ def test_rotations_match_oracle(ks_setup, level, hoisted):
         assert np.abs(orc.decrypt(got, level, s_ntt, 2.0 ** 40) - np.roll(z, -r)).max() < 1e-5
 
 
+def test_unhoisted_rotations_batch_to_fit_the_workspace(ks_setup):
+    """Unhoisted rotations go through the kernels in batches as large as the workspace holds: the workspace of a
+    single rotation (one at a time), of three (batches of 3, 3, 1) and the full one give the oracle's residues."""
+    p, orc, ctx, s, s_ntt, rlk, d_rlk = ks_setup
+    level = 5
+    ct = orc.encrypt(np.random.default_rng(35).uniform(-1, 1, orc.n), 2.0 ** 40, level, s_ntt, 36)
+    offs = [3, -2, 17, 0, 900, -77, 5, 2048]
+    keys = [orc.gen_rotation_key(s, s_ntt, r, 60 + i) if r % orc.n else None for i, r in enumerate(offs)]
+    dkeys = [hx.ckks_key_load(ctx, hx.from_host(k), hx.ckks_galois_element(ctx, r)) if k is not None else None
+             for k, r in zip(keys, offs)]
+    want = orc.rotate_many(ct, level, offs, keys, False)
+    d_ct = hx.from_host(ct)
+    for count in (1, 3, len(offs)):
+        nbytes = hx.ckks_workspace_bytes(ctx, hx.binding.CKKS_OP_ROTATE, level, count)
+        ws = hx.empty((nbytes + 7) // 8)
+        outs = hx.ckks_rotate_hoisted(ctx, d_ct, level, offs, dkeys, False, ws=ws)
+        for r, got, w in zip(offs, outs, want):
+            assert np.array_equal(hx.to_host(got), w), f"workspace for {count}, offset {r}"
+    with pytest.raises(hx.CkksError) as e:
+        hx.ckks_rotate_hoisted(ctx, d_ct, level, offs, dkeys, False, ws=hx.empty(1024))
+    assert e.value.code == hx.binding.CKKS_ERR_WORKSPACE_TOO_SMALL
+
+
 def test_galois_element_matches_oracle(ks_setup):
     p, orc, ctx, *_ = ks_setup
     for r in (0, 1, -1, 5, orc.n - 1, orc.n, -orc.n - 3, 2 ** 20 + 7):
