@@ -109,7 +109,9 @@ size_t ws_ctct(const ckks_ctx* c, u32 level, u32 n) { return 3 * blk((size_t)n *
 
 // Decompose + ModUp of n <= CT_BATCH polynomials srcs[b] ([level+1][N], NTT form) into
 // ws.digits + b*ws.dig_b ([beta][E][N], NTT form).
-int run_modup(const ckks_ctx* c, u32 level, const u64* const* srcs, u32 n, const KsWs& ws, hipStream_t st) {
+// hi_only (double-precision transforms only): the forward transforms stop after their first pass; the caller finishes them
+// inside the inner product (launch_ntt_lo_mac).
+int run_modup(const ckks_ctx* c, u32 level, const u64* const* srcs, u32 n, const KsWs& ws, hipStream_t st, bool hi_only = false) {
     const u32 N = c->N, L1 = level + 1, E = c->ext_limbs(level), beta = c->live_digits(level);
     for (u32 b = 0; b < CT_BATCH; b++) ws.own[b] = b < n ? srcs[b] : nullptr;
     // all live limbs of every polynomial to coefficient form at once.  With double-precision transforms the inverse scales
@@ -117,6 +119,7 @@ int run_modup(const ckks_ctx* c, u32 level, const u64* const* srcs, u32 n, const
     // inside the first pass of the forward transforms of its target limbs (no conversion kernel, no coefficient-form copy
     // of the extended digit).
     const bool fused = ntt_has_modup(c);
+    if (hi_only && !fused) return set_err(c, CKKS_ERR_INVALID_ARG, "internal: fused inner product without fused ModUp");
     HIP_TRY(launch_ntt(c, true, nullptr, 0, ws.y, L1, range_list(0, L1, 0), n, st, srcs, nullptr,
                        fused ? c->d_modup_prep_f + (size_t)level * c->num_q : nullptr));  // (positions 0..level are moduli 0..level)
     const PtrList8 cl = ptr_list(srcs, n);
@@ -134,7 +137,7 @@ int run_modup(const ckks_ctx* c, u32 level, const u64* const* srcs, u32 n, const
             pl.n++;
         }
         for (u32 a = pl.n; a < CKKS_MAX_MODULI; a++) pl.spos[a] = pl.dpos[a] = pl.mod[a] = 0;
-        if (fused) HIP_TRY(launch_ntt_modup(c, level, j, (const double*)ws.y, ws.y_b, digit, (size_t)beta * E, pl, n, st));
+        if (fused) HIP_TRY(launch_ntt_modup(c, level, j, (const double*)ws.y, ws.y_b, digit, (size_t)beta * E, pl, n, st, hi_only));
         else HIP_TRY(launch_ntt(c, false, digit, (size_t)beta * E, digit, (size_t)beta * E, pl, n, st));
     }
     return CKKS_OK;
@@ -237,9 +240,20 @@ int run_ctct(const ckks_ctx* c, u32 level, const u64* const* a, size_t a_cstride
         d2s[i] = d2 + i * L1 * N;
         items[i] = FinalItem{d0 + i * L1 * N, d1 + i * L1 * N, nullptr, outs[i], 1, 0};
     }
-    int rc = run_modup(c, level, d2s, n, ws, st);
+    const bool mac = ntt_has_modup(c);  // the inner product inside the forward transforms' second pass
+    int rc = run_modup(c, level, d2s, n, ws, st, mac);
     if (rc) return rc;
-    HIP_TRY(launch_key_inner_multi(c, level, dsrc(c, ws, 0), d_rlk, 1, ws.v, ws.v_b, n, st));
+    if (mac) {
+        const u64* keys[CT_BATCH];
+        u64* vs[CT_BATCH];
+        for (u32 i = 0; i < n; i++) {
+            keys[i] = d_rlk;
+            vs[i] = ws.v + i * ws.v_b;
+        }
+        HIP_TRY(launch_ntt_lo_mac(c, level, dsrc(c, ws, 0), keys, nullptr, nullptr, vs, n, st));
+    } else {
+        HIP_TRY(launch_key_inner_multi(c, level, dsrc(c, ws, 0), d_rlk, 1, ws.v, ws.v_b, n, st));
+    }
     return run_moddown(c, level, ws, n, items, st);
 }
 
@@ -266,9 +280,16 @@ int run_ctct_merged(const ckks_ctx* c, u32 level, const u64* const* a, size_t a_
         vs[i] = ws.v + i * ws.v_b;
         items[i] = FinalItem{nullptr, nullptr, nullptr, outs[i], 1, 0};
     }
-    int rc = run_modup(c, level, d2s, n, ws, st);
+    const bool mac = ntt_has_modup(c);  // the inner product inside the forward transforms' second pass
+    int rc = run_modup(c, level, d2s, n, ws, st, mac);
     if (rc) return rc;
-    HIP_TRY(launch_key_inner_ext(c, level, dsrc(c, ws, 0), d_rlk, 1, add0, add1, nullptr, vs, n, st));
+    if (mac) {
+        const u64* keys[CT_BATCH];
+        for (u32 i = 0; i < n; i++) keys[i] = d_rlk;
+        HIP_TRY(launch_ntt_lo_mac(c, level, dsrc(c, ws, 0), keys, add0, add1, vs, n, st));
+    } else {
+        HIP_TRY(launch_key_inner_ext(c, level, dsrc(c, ws, 0), d_rlk, 1, add0, add1, nullptr, vs, n, st));
+    }
     return run_moddown(c, level, ws, n, items, st, true);
 }
 
@@ -836,9 +857,15 @@ int ckks_keyswitch(const ckks_ctx* c, const uint64_t* d_c, uint32_t level, const
     if (!carve_ks(c, level, 1, 1, ar, ws)) return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for key switch");
     hipStream_t st = (hipStream_t)stream;
     const u64* src = (const u64*)d_c;
-    int rc = run_modup(c, level, &src, 1, ws, st);
+    const bool mac = ntt_has_modup(c);
+    int rc = run_modup(c, level, &src, 1, ws, st, mac);
     if (rc) return rc;
-    HIP_TRY(launch_key_inner(c, level, dsrc(c, ws, 0), key->d_key, 1, ws.v, st));
+    if (mac) {
+        const u64* k = key->d_key;
+        HIP_TRY(launch_ntt_lo_mac(c, level, dsrc(c, ws, 0), &k, nullptr, nullptr, &ws.v, 1, st));
+    } else {
+        HIP_TRY(launch_key_inner(c, level, dsrc(c, ws, 0), key->d_key, 1, ws.v, st));
+    }
     const FinalItem item = {nullptr, nullptr, nullptr, (u64*)d_out, 1, 0};
     return run_moddown(c, level, ws, 1, &item, st);
 }
@@ -923,10 +950,21 @@ int ckks_rotate_hoisted(const ckks_ctx* c, const uint64_t* d_ct, uint32_t level,
             HIP_TRY(launch_automorph(c, (u32)L1, c1, items[b].g, dst, st));
             srcs[b] = dst;
         }
-        int rc = run_modup(c, level, srcs, nb, ws, st);
+        const bool mac = ntt_has_modup(c);
+        int rc = run_modup(c, level, srcs, nb, ws, st, mac);
         if (rc) return rc;
         // the digits already belong to sigma_g(c1): no gather in the inner product, only on c0
-        for (u32 b = 0; b < nb; b++) HIP_TRY(launch_key_inner(c, level, dsrc(c, ws, b), pend_key[b]->d_key, 1, ws.v + b * ws.v_b, st));
+        if (mac) {  // every item with its own key, inside the forward transforms' second pass
+            const u64* ks[CT_BATCH];
+            u64* vs[CT_BATCH];
+            for (u32 b = 0; b < nb; b++) {
+                ks[b] = pend_key[b]->d_key;
+                vs[b] = ws.v + b * ws.v_b;
+            }
+            HIP_TRY(launch_ntt_lo_mac(c, level, dsrc(c, ws, 0), ks, nullptr, nullptr, vs, nb, st));
+        } else {
+            for (u32 b = 0; b < nb; b++) HIP_TRY(launch_key_inner(c, level, dsrc(c, ws, b), pend_key[b]->d_key, 1, ws.v + b * ws.v_b, st));
+        }
         rc = run_moddown(c, level, ws, nb, items, st);
         nb = 0;
         return rc;

@@ -212,8 +212,13 @@ inline bool ntt_has_modup(const ckks_ctx* c) { return c->ntt_f64 && c->log_n > C
 // NTT form), epilogue what the second pass does with it.  merged: the dropped set is {q_level, p_0..p_{k-1}}.
 hipError_t launch_ntt_moddown(const ckks_ctx* c, u32 level, bool merged, const double* y, u64* dst, u32 batch, hipStream_t st,
                               const FwdEpilogue* epilogue);
+// hi_only: stop after the converting hi pass; launch_ntt_lo_mac then runs the lo passes of all digits and multiplies the
+// results by the switching keys (keys[b]: [dnum][2][M][N], one per batch item) as they come out, adding P * add0s[b] /
+// add1s[b] (optional, [level+1][N]) on the q-limbs: outs[b] [2][E][N] is the finished inner product on the extended basis.
 hipError_t launch_ntt_modup(const ckks_ctx* c, u32 level, u32 j, const double* y, size_t y_bstride, u64* dst, size_t dst_bstride,
-                            const PolyList& pl, u32 batch, hipStream_t st);
+                            const PolyList& pl, u32 batch, hipStream_t st, bool hi_only = false);
+hipError_t launch_ntt_lo_mac(const ckks_ctx* c, u32 level, const DigitSrc& digits, const u64* const* keys, const u64* const* add0s,
+                             const u64* const* add1s, u64* const* outs, u32 n, hipStream_t st);
 // whether launch_ntt can apply an epilogue in this ring (it needs the two-pass transform)
 inline bool ntt_has_epilogue(const ckks_ctx* c) { return c->log_n > CKKS_TILE_LOG; }
 // keyswitch.hip

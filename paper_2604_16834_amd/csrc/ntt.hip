@@ -88,6 +88,14 @@ struct ArithF64 {
         const double c = round_mul(y, wq);
         return __builtin_fma(-c, q, h) + l;
     }
+    // the same for a multiplier without a precomputed w / q (a key word, a ciphertext residue): the quotient comes from
+    // the rounded product, |y| < q, 0 <= w < q; exact, magnitude below 0.57 q (host check against 128-bit integers)
+    static __device__ __forceinline__ double mulmod_any(double y, double w, double q, double qinv) {
+        const double h = y * w;
+        const double l = __builtin_fma(y, w, -h);
+        const double c = round_mul(h, qinv);
+        return __builtin_fma(-c, q, h) + l;
+    }
     // canonical residues below 2^52 <-> doubles through the mantissa of 2^52 + v
     static __device__ __forceinline__ double from_u64(u64 raw) { return __longlong_as_double((long long)(raw | 0x4330000000000000ull)) - F64_2P52; }
     static __device__ __forceinline__ u64 to_u64(double v) { return (u64)__double_as_longlong(v + F64_2P52) & 0x000fffffffffffffull; }
@@ -379,6 +387,143 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_kernel(NttArgs args, P
 template <class A, int IT>
 __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_div_kernel(NttArgs args, PolyList pl, FwdEpilogue ep) {
     fwd_lo_body<A, IT, true>(args, pl, ep);
+}
+
+// The lo pass of ModUp's forward transforms with the inner product with the switching key in place of its stores.
+// A workgroup owns one 2^11-point slice of one position e of the extended basis of one batch item: it transforms that
+// slice of every digit whose limb e went through the converting hi pass (all live digits but the one e belongs to; the
+// slice's twiddles are fetched once for all of them), multiplies each result by the two key words of (digit, e) as it
+// comes out, adds the product of the digit that owns e (its limb is the decomposed polynomial's own, never transformed)
+// and, on the q-limbs, P times the optional addends, and stores the two components of the inner product: the extended
+// digits are never written in evaluation form nor read back.  All sums are exact integers in doubles (at most
+// beta + 1 terms below 0.57 q each).
+struct MacEpilogue {
+    DigitSrc D;           // D.digits: rows (j*E + e) hold the hi pass' output (doubles); D.own: the decomposed polynomials
+    PtrList8 key;         // per batch item: [dnum][2][M][N] (the same pointer for a shared key)
+    PtrList8 add0, add1;  // per batch item, optional: [level+1][N]
+    OutList8 out;         // per batch item: [2][E][N]
+    const u64* negp;      // [num_q]: -P mod q_i
+    u32 level, M, E, beta;
+};
+
+__global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_mac_kernel(NttArgs args, PolyList pl, MacEpilogue ep) {
+    typedef ArithF64 A;
+    typedef double E;
+    __shared__ E lds0[LDS_PADDED_WORDS];
+    __shared__ E lds1[LDS_PADDED_WORDS];
+    const u32 tid = threadIdx.x;
+    const LoTile tile = lo_tile(args.log_hi, args.lo_group);
+    const u32 blk = tile.blk, b = tile.b, e = tile.a, m_idx = pl.mod[e];
+    const size_t N = (size_t)1 << args.log_n, off = (size_t)blk << 11;
+    const TwF* tw = (const TwF*)args.tw + ((size_t)m_idx << args.log_n);
+    const ModConstF mc = ((const ModConstF*)args.mc)[m_idx];
+    const u32 own = e <= ep.level ? e / ep.D.alpha : 0xffffffffu;  // the digit that limb e belongs to
+    const u32 TA = (1u << args.log_hi) + blk;
+    const u32 d3 = tid >> 5, x5 = tid & 31, d2 = (tid >> 2) & 7, d0 = tid & 3;
+    const u64* key = ep.key.p[b] + (size_t)m_idx * N + off;
+    const size_t kstride = (size_t)ep.M * N;  // between the b and the a part of a digit's key; two of them per digit
+    const double* hi = (const double*)(ep.D.digits + b * ep.D.bstride) + (size_t)e * N + off;
+    const size_t dstride = (size_t)ep.E * N;
+    E acc0[8], acc1[8];
+#pragma unroll
+    for (int j = 0; j < 8; j++) acc0[j] = acc1[j] = 0.0;
+    TwF wa[7], wb[7], wc[7], wd[6];  // the slice's twiddles, fetched once for all digits
+    load_tw<A, 3>(tw, TA, wa);
+    load_tw<A, 3>(tw, 8 * TA + d3, wb);
+    load_tw<A, 3>(tw, 64 * TA + 8 * d3 + d2, wc);
+    load_tw<A, 2>(tw, 512 * TA + 2 * tid, wd);
+    load_tw<A, 2>(tw, 512 * TA + 2 * tid + 1, wd + 3);
+    u32 j = own == 0 ? 1 : 0;  // first digit to transform
+    E v[8], raw[8];
+    if (j < ep.beta) {
+#pragma unroll
+        for (int i = 0; i < 8; i++) raw[i] = hi[(size_t)j * dstride + tid + 256 * i];
+    }
+    while (j < ep.beta) {
+        u32 jn = j + 1;
+        if (jn == own) jn++;
+#pragma unroll
+        for (int i = 0; i < 8; i++) v[i] = raw[i];
+        if (jn < ep.beta) {  // the next digit's points, a tile ahead
+#pragma unroll
+            for (int i = 0; i < 8; i++) raw[i] = hi[(size_t)jn * dstride + tid + 256 * i];
+        }
+        fwd_rows_pre<A, 3>(v, wa, mc);
+        A::fwd_round_end(v, mc);
+#pragma unroll
+        for (int i = 0; i < 8; i++) lds0[LDS_PAD(tid + 256 * i)] = v[i];
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 8; i++) v[i] = lds0[LDS_PAD(d3 * 256 + 32 * i + x5)];
+        fwd_rows_pre<A, 3>(v, wb, mc);
+        A::fwd_round_end(v, mc);
+#pragma unroll
+        for (int i = 0; i < 8; i++) lds1[LDS_PAD(d3 * 256 + 32 * i + x5)] = v[i];
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 8; i++) v[i] = lds1[LDS_PAD(d3 * 256 + d2 * 32 + 4 * i + d0)];
+        fwd_rows_pre<A, 3>(v, wc, mc);
+        A::fwd_round_end(v, mc);
+#pragma unroll
+        for (int i = 0; i < 8; i++) lds0[LDS_PAD(d3 * 256 + d2 * 32 + 4 * i + d0)] = v[i];
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 8; i++) v[i] = lds0[LDS_PAD(8 * tid + i)];
+        // the key words of this digit at the points this thread ends up with: requested now, needed after the last round
+        u64 k0[8], k1[8];
+        {
+            const u64* kj = key + (size_t)j * 2 * kstride;
+#pragma unroll
+            for (int i = 0; i < 8; i++) {
+                k0[i] = kj[tid + 256 * i];
+                k1[i] = kj[kstride + tid + 256 * i];
+            }
+        }
+        fwd_rows_pre<A, 2>(v, wd, mc);
+        fwd_rows_pre<A, 2>(v + 4, wd + 3, mc);
+        A::fwd_round_end(v, mc);
+        // back through LDS: point tid + 256 i of the slice, where the key words were fetched
+#pragma unroll
+        for (int i = 0; i < 8; i++) lds1[LDS_PAD(8 * tid + i)] = v[i];
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+            const double y = lds1[LDS_PAD(tid + 256 * i)];
+            acc0[i] += A::mulmod_any(y, A::from_u64(k0[i]), mc.q, mc.qinv);
+            acc1[i] += A::mulmod_any(y, A::from_u64(k1[i]), mc.q, mc.qinv);
+        }
+        j = jn;
+    }
+    if (e <= ep.level) {
+        {  // the digit that owns this limb
+            const u64* kj = key + (size_t)own * 2 * kstride;
+            const u64* yo = ep.D.own.p[b] + (size_t)e * N + off;
+#pragma unroll
+            for (int i = 0; i < 8; i++) {
+                const double y = A::from_u64(yo[tid + 256 * i]);
+                acc0[i] += A::mulmod_any(y, A::from_u64(kj[tid + 256 * i]), mc.q, mc.qinv);
+                acc1[i] += A::mulmod_any(y, A::from_u64(kj[kstride + tid + 256 * i]), mc.q, mc.qinv);
+            }
+        }
+        const double pres = mc.q - A::from_u64(ep.negp[e]);  // P mod q_e
+        const u64* a0 = ep.add0.p[b];
+        const u64* a1 = ep.add1.p[b];
+        if (a0) {
+#pragma unroll
+            for (int i = 0; i < 8; i++) acc0[i] += A::mulmod_any(A::from_u64(a0[(size_t)e * N + off + tid + 256 * i]), pres, mc.q, mc.qinv);
+        }
+        if (a1) {
+#pragma unroll
+            for (int i = 0; i < 8; i++) acc1[i] += A::mulmod_any(A::from_u64(a1[(size_t)e * N + off + tid + 256 * i]), pres, mc.q, mc.qinv);
+        }
+    }
+    u64* o0 = ep.out.p[b] + (size_t)e * N + off;
+    u64* o1 = o0 + (size_t)ep.E * N;
+#pragma unroll
+    for (int i = 0; i < 8; i++) {
+        o0[tid + 256 * i] = A::canonical(A::reduce(acc0[i], mc), mc);
+        o1[tid + 256 * i] = A::canonical(A::reduce(acc1[i], mc), mc);
+    }
 }
 
 template <class A, int IT>
@@ -760,8 +905,9 @@ static void launch_hi_conv(u32 log_hi, u32 ap, dim3 grid, hipStream_t st, const 
 
 static hipError_t launch_ntt_any(const ckks_ctx* c, bool inverse, const u64* src, size_t src_bstride, u64* dst,
                                  size_t dst_bstride, const PolyList& pl, u32 batch, hipStream_t st, const u64* const* src_ptrs,
-                                 const FwdEpilogue* epilogue, const TwF* inv_scale, const ConvPrologue* conv) {
+                                 const FwdEpilogue* epilogue, const TwF* inv_scale, const ConvPrologue* conv, bool hi_only = false) {
     if (pl.n == 0 || batch == 0) return hipSuccess;
+    if (hi_only && (!conv || epilogue)) return hipErrorInvalidValue;
     if (src_ptrs && batch > KS_MAX_BATCH) return hipErrorInvalidValue;
     if (epilogue && (inverse || !ntt_has_epilogue(c) || batch > 2 * KS_MAX_BATCH)) return hipErrorInvalidValue;
     if ((inv_scale && !inverse) || (conv && inverse) || ((inv_scale || conv) && !ntt_has_modup(c))) return hipErrorInvalidValue;
@@ -826,6 +972,7 @@ static hipError_t launch_ntt_any(const ckks_ctx* c, bool inverse, const u64* src
                 ProfScope ps__(c, K_NTT_FWD_HI, st, pass_bytes, hi_ops);
                 hi(args, pl);
             }
+            if (hi_only) return hipGetLastError();  // the caller's own lo pass follows (launch_ntt_lo_mac)
             if (epilogue) {  // reads w and v, writes the quotients (plus the addends it reads)
                 ProfScope ps__(c, K_NTT_FWD_LO, st, 1.5 * pass_bytes, lo_ops);
                 if (f64) launch_lo_div<ArithF64>(lo_items, grid_lo, st, second, pd, *epilogue);
@@ -853,7 +1000,7 @@ hipError_t launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, size_t sr
 }
 
 hipError_t launch_ntt_modup(const ckks_ctx* c, u32 level, u32 j, const double* y, size_t y_bstride, u64* dst, size_t dst_bstride,
-                            const PolyList& pl, u32 batch, hipStream_t st) {
+                            const PolyList& pl, u32 batch, hipStream_t st, bool hi_only) {
     ConvPrologue cp;
     cp.y = y;
     cp.y_bstride = y_bstride;
@@ -862,7 +1009,52 @@ hipError_t launch_ntt_modup(const ckks_ctx* c, u32 level, u32 j, const double* y
     cp.nd = c->digit_hi(j, level) - cp.lo;
     cp.ap = c->alpha_pad;
     cp.pad = 0;
-    return launch_ntt_any(c, false, dst, dst_bstride, dst, dst_bstride, pl, batch, st, nullptr, nullptr, nullptr, &cp);
+    return launch_ntt_any(c, false, dst, dst_bstride, dst, dst_bstride, pl, batch, st, nullptr, nullptr, nullptr, &cp, hi_only);
+}
+
+hipError_t launch_ntt_lo_mac(const ckks_ctx* c, u32 level, const DigitSrc& digits, const u64* const* keys, const u64* const* add0s,
+                             const u64* const* add1s, u64* const* outs, u32 n, hipStream_t st) {
+    if (!ntt_has_modup(c) || c->log_hi == 0 || n == 0 || n > KS_MAX_BATCH) return hipErrorInvalidValue;
+    const u32 E = c->ext_limbs(level), beta = c->live_digits(level);
+    NttArgs args = {};
+    args.mc = c->d_mcf;
+    args.tw = c->d_twf;
+    args.log_n = c->log_n;
+    args.log_lo = c->log_lo;
+    args.log_hi = c->log_hi;
+    args.batch = n;
+    const u32 slices = E << c->log_hi;
+    args.lo_group = 0;
+    for (u32 g = 64; g >= 8; g >>= 1)
+        if (slices % g == 0) { args.lo_group = g; break; }
+    PolyList pl;
+    pl.n = E;
+    for (u32 e = 0; e < CKKS_MAX_MODULI; e++) pl.spos[e] = pl.dpos[e] = pl.mod[e] = (unsigned char)(e < E ? c->ext_modulus(level, e) : 0);
+    MacEpilogue ep;
+    ep.D = digits;
+    double n_add = 0.0, n_keys = 0.0;
+    for (u32 b = 0; b < KS_MAX_BATCH; b++) {
+        ep.key.p[b] = b < n ? keys[b] : nullptr;
+        ep.add0.p[b] = (b < n && add0s) ? add0s[b] : nullptr;
+        ep.add1.p[b] = (b < n && add1s) ? add1s[b] : nullptr;
+        ep.out.p[b] = b < n ? outs[b] : nullptr;
+        if (b < n && !ep.key.p[b]) return hipErrorInvalidValue;
+        n_add += (ep.add0.p[b] ? 1.0 : 0.0) + (ep.add1.p[b] ? 1.0 : 0.0);
+        if (b < n && (b == 0 || keys[b] != keys[b - 1])) n_keys += 1.0;
+    }
+    ep.negp = c->d_moddown + 2 * c->k_pad + (size_t)c->k_pad * c->num_q + 2 * c->num_q;
+    ep.level = level;
+    ep.M = c->M;
+    ep.E = E;
+    ep.beta = beta;
+    // digits transformed per batch item: every (digit, position) pair but the digits' own limbs
+    const double n_tr = (double)beta * E - (level + 1.0);
+    const dim3 grid = args.lo_group ? dim3(args.lo_group, n, slices / args.lo_group) : dim3(n, slices);
+    // in: the transformed rows, the own limbs, the addends, the keys (once per distinct key); out: two components
+    ProfScope ps__(c, K_NTT_FWD_LO, st, 8.0 * c->N * (n * (n_tr + (level + 1.0) + 2.0 * E) + n_add * (level + 1.0) + n_keys * 2.0 * beta * E),
+                   0.5 * n * n_tr * c->N * c->log_lo);
+    hipLaunchKernelGGL(ntt_fwd_lo_mac_kernel, grid, dim3(NTT_THREADS), 0, st, args, pl, ep);
+    return hipGetLastError();
 }
 
 hipError_t launch_ntt_moddown(const ckks_ctx* c, u32 level, bool merged, const double* y, u64* dst, u32 batch, hipStream_t st,
