@@ -111,9 +111,12 @@ size_t ws_ctct(const ckks_ctx* c, u32 level, u32 n) { return 3 * blk((size_t)n *
 // ws.digits + b*ws.dig_b ([beta][E][N], NTT form).
 // hi_only (double-precision transforms only): the forward transforms stop after their first pass; the caller finishes them
 // inside the inner product (launch_ntt_lo_mac).
-int run_modup(const ckks_ctx* c, u32 level, const u64* const* srcs, u32 n, const KsWs& ws, hipStream_t st, bool hi_only = false) {
+// muls (with hi_only): the polynomial to decompose is srcs[b] (.) muls[b], formed as the inverse transform loads it.
+int run_modup(const ckks_ctx* c, u32 level, const u64* const* srcs, u32 n, const KsWs& ws, hipStream_t st, bool hi_only = false,
+              const u64* const* muls = nullptr) {
     const u32 N = c->N, L1 = level + 1, E = c->ext_limbs(level), beta = c->live_digits(level);
-    for (u32 b = 0; b < CT_BATCH; b++) ws.own[b] = b < n ? srcs[b] : nullptr;
+    for (u32 b = 0; b < CT_BATCH; b++) ws.own[b] = (b < n && !muls) ? srcs[b] : nullptr;  // a product has no stored own limbs
+    if (muls && !hi_only) return set_err(c, CKKS_ERR_INVALID_ARG, "internal: product source without the fused inner product");
     // all live limbs of every polynomial to coefficient form at once.  With double-precision transforms the inverse scales
     // limb i by N^-1 (Q_j/q_i)^-1 and leaves the centred residue as a double, and each digit's basis conversion happens
     // inside the first pass of the forward transforms of its target limbs (no conversion kernel, no coefficient-form copy
@@ -121,7 +124,7 @@ int run_modup(const ckks_ctx* c, u32 level, const u64* const* srcs, u32 n, const
     const bool fused = ntt_has_modup(c);
     if (hi_only && !fused) return set_err(c, CKKS_ERR_INVALID_ARG, "internal: fused inner product without fused ModUp");
     HIP_TRY(launch_ntt(c, true, nullptr, 0, ws.y, L1, range_list(0, L1, 0), n, st, srcs, nullptr,
-                       fused ? c->d_modup_prep_f + (size_t)level * c->num_q : nullptr));  // (positions 0..level are moduli 0..level)
+                       fused ? c->d_modup_prep_f + (size_t)level * c->num_q : nullptr, muls));  // (positions 0..level are moduli 0..level)
     const PtrList8 cl = ptr_list(srcs, n);
     for (u32 j = 0; j < beta; j++) {
         const u32 lo = c->digit_lo(j), hi = c->digit_hi(j, level);
@@ -269,10 +272,30 @@ int run_ctct_merged(const ckks_ctx* c, u32 level, const u64* const* a, size_t a_
     u64* d2 = ar.take(n * L1 * N);
     KsWs ws;
     if (!carve_ks(c, level, n, n, ar, ws)) return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for ct-ct multiply");
-    HIP_TRY(launch_tensor(c, level, ptr_list(a, n), a_cstride, ptr_list(b, n), b_cstride, d0, d1, d2, n, addend, add_bstride, st));
+    const bool mac = ntt_has_modup(c);  // the inner product inside the forward transforms' second pass
     const u64 *d2s[CT_BATCH], *add0[CT_BATCH], *add1[CT_BATCH];
     u64* vs[CT_BATCH];
     FinalItem items[CT_BATCH];
+    if (mac) {
+        // no tensor-product kernel either: d2 = a1 (.) b1 is formed as the inverse transform loads it, d0, d1 and the own-limb
+        // term as the inner product's last terms, all from the operands themselves
+        const u64 *a1[CT_BATCH], *b1[CT_BATCH], *keys[CT_BATCH];
+        for (u32 i = 0; i < n; i++) {
+            a1[i] = a[i] + a_cstride;
+            b1[i] = b[i] + b_cstride;
+            add0[i] = addend ? addend + i * add_bstride : nullptr;
+            add1[i] = addend ? addend + i * add_bstride + L1 * N : nullptr;
+            vs[i] = ws.v + i * ws.v_b;
+            keys[i] = d_rlk;
+            items[i] = FinalItem{nullptr, nullptr, nullptr, outs[i], 1, 0};
+        }
+        int rc = run_modup(c, level, a1, n, ws, st, true, b1);
+        if (rc) return rc;
+        const MacProduct prod = {a, a1, b, b1};
+        HIP_TRY(launch_ntt_lo_mac(c, level, dsrc(c, ws, 0), keys, addend ? add0 : nullptr, addend ? add1 : nullptr, vs, n, st, &prod));
+        return run_moddown(c, level, ws, n, items, st, true);
+    }
+    HIP_TRY(launch_tensor(c, level, ptr_list(a, n), a_cstride, ptr_list(b, n), b_cstride, d0, d1, d2, n, addend, add_bstride, st));
     for (u32 i = 0; i < n; i++) {
         d2s[i] = d2 + i * L1 * N;
         add0[i] = d0 + i * L1 * N;
@@ -280,16 +303,9 @@ int run_ctct_merged(const ckks_ctx* c, u32 level, const u64* const* a, size_t a_
         vs[i] = ws.v + i * ws.v_b;
         items[i] = FinalItem{nullptr, nullptr, nullptr, outs[i], 1, 0};
     }
-    const bool mac = ntt_has_modup(c);  // the inner product inside the forward transforms' second pass
-    int rc = run_modup(c, level, d2s, n, ws, st, mac);
+    int rc = run_modup(c, level, d2s, n, ws, st);
     if (rc) return rc;
-    if (mac) {
-        const u64* keys[CT_BATCH];
-        for (u32 i = 0; i < n; i++) keys[i] = d_rlk;
-        HIP_TRY(launch_ntt_lo_mac(c, level, dsrc(c, ws, 0), keys, add0, add1, vs, n, st));
-    } else {
-        HIP_TRY(launch_key_inner_ext(c, level, dsrc(c, ws, 0), d_rlk, 1, add0, add1, nullptr, vs, n, st));
-    }
+    HIP_TRY(launch_key_inner_ext(c, level, dsrc(c, ws, 0), d_rlk, 1, add0, add1, nullptr, vs, n, st));
     return run_moddown(c, level, ws, n, items, st, true);
 }
 

@@ -201,7 +201,7 @@ struct ProfScope {
 // array of `batch` <= KS_MAX_BATCH device pointers) and writes dst + b*dst_bstride*N
 hipError_t launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, size_t src_bstride, u64* dst,
                       size_t dst_bstride, const PolyList& pl, u32 batch, hipStream_t st, const u64* const* src_ptrs = nullptr,
-                      const FwdEpilogue* epilogue = nullptr, const TwF* inv_scale = nullptr);
+                      const FwdEpilogue* epilogue = nullptr, const TwF* inv_scale = nullptr, const u64* const* mul_ptrs = nullptr);
 // ModUp fused into transforms (contexts with ntt_f64 and the two-pass transform): the inverse transform of the polynomial
 // scales the limb with modulus index m by inv_scale[m] instead of 1/N and stores the CENTRED residue as a double (launch_ntt with inv_scale);
 // launch_ntt_modup then evaluates the basis conversion of digit j, y [batch][level+1][N] doubles -> the pl.n target limbs
@@ -217,8 +217,18 @@ hipError_t launch_ntt_moddown(const ckks_ctx* c, u32 level, bool merged, const d
 // add1s[b] (optional, [level+1][N]) on the q-limbs: outs[b] [2][E][N] is the finished inner product on the extended basis.
 hipError_t launch_ntt_modup(const ckks_ctx* c, u32 level, u32 j, const double* y, size_t y_bstride, u64* dst, size_t dst_bstride,
                             const PolyList& pl, u32 batch, hipStream_t st, bool hi_only = false);
+// prod: the decomposed polynomial is the d2 = a1 (.) b1 of n ciphertext products and was never stored (the inverse
+// transform took it as a product, launch_ntt with mul_ptrs): the term of the digits' own limbs and the addends
+// d0 = a0 (.) b0 + add0, d1 = a0 (.) b1 + a1 (.) b0 + add1 are formed from the operands (host arrays of n device pointers,
+// [level+1][N] each).
+struct MacProduct {
+    const u64* const* a0;
+    const u64* const* a1;
+    const u64* const* b0;
+    const u64* const* b1;
+};
 hipError_t launch_ntt_lo_mac(const ckks_ctx* c, u32 level, const DigitSrc& digits, const u64* const* keys, const u64* const* add0s,
-                             const u64* const* add1s, u64* const* outs, u32 n, hipStream_t st);
+                             const u64* const* add1s, u64* const* outs, u32 n, hipStream_t st, const MacProduct* prod = nullptr);
 // whether launch_ntt can apply an epilogue in this ring (it needs the two-pass transform)
 inline bool ntt_has_epilogue(const ckks_ctx* c) { return c->log_n > CKKS_TILE_LOG; }
 // keyswitch.hip

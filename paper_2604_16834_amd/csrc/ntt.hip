@@ -206,6 +206,7 @@ struct NttArgs {
     u32 lo_group;        // slices per group of the lo-pass numbering (0: plain)
     u32 use_src_list;    // batch item b reads src_list.p[b] instead of src + b*src_bstride*N
     PtrList8 src_list;
+    PtrList8 mul_list;     // inverse, first pass, product variant: batch item b is src_list.p[b] (.) mul_list.p[b]
     const TwF* inv_scale;  // inverse, last pass (double-precision arithmetic): the limb of modulus m is scaled by inv_scale[m]
                            // instead of 1/N and stored as the centred residue in a double (the form ModUp's conversion reads)
 };
@@ -404,6 +405,11 @@ struct MacEpilogue {
     OutList8 out;         // per batch item: [2][E][N]
     const u64* negp;      // [num_q]: -P mod q_i
     u32 level, M, E, beta;
+    // prod != 0: the decomposed polynomial is d2 = a1 (.) b1 of the ciphertext product (a0, a1) x (b0, b1), which exists
+    // nowhere in evaluation form: the own-limb term is formed from a1, b1 ([level+1][N] each, per batch item), and the
+    // addends are d0 = a0 (.) b0 + add0 and d1 = a0 (.) b1 + a1 (.) b0 + add1 (D.own is not read)
+    PtrList8 a0, a1, b0, b1;
+    u32 prod, pad;
 };
 
 __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_mac_kernel(NttArgs args, PolyList pl, MacEpilogue ep) {
@@ -494,7 +500,29 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_mac_kernel(NttArgs arg
         }
         j = jn;
     }
-    if (e <= ep.level) {
+    if (e <= ep.level && ep.prod) {
+        // the tensor product of this slice, formed here: d2 feeds the digit that owns the limb, P d0 and P d1 join the sums
+        const u64* kj = key + (size_t)own * 2 * kstride;
+        const size_t po = (size_t)e * N + off;
+        const u64 *pa0 = ep.a0.p[b] + po, *pa1 = ep.a1.p[b] + po, *pb0 = ep.b0.p[b] + po, *pb1 = ep.b1.p[b] + po;
+        const u64* c0 = ep.add0.p[b];
+        const u64* c1 = ep.add1.p[b];
+        const double pres = mc.q - A::from_u64(ep.negp[e]);  // P mod q_e
+#pragma unroll
+        for (int i = 0; i < 8; i++) {
+            const u32 x = tid + 256 * i;
+            const double A0 = A::from_u64(pa0[x]), A1 = A::from_u64(pa1[x]), B0 = A::from_u64(pb0[x]), B1 = A::from_u64(pb1[x]);
+            const double dd2 = A::mulmod_any(A1, B1, mc.q, mc.qinv);
+            double dd0 = A::mulmod_any(A0, B0, mc.q, mc.qinv);
+            double dd1 = A::mulmod_any(A0, B1, mc.q, mc.qinv) + A::mulmod_any(A1, B0, mc.q, mc.qinv);
+            if (c0) dd0 += A::from_u64(c0[po + x]);
+            if (c1) dd1 += A::from_u64(c1[po + x]);
+            dd0 = A::reduce(dd0, mc);  // back below q / 2 + 1 as multiplicands
+            dd1 = A::reduce(dd1, mc);
+            acc0[i] += A::mulmod_any(dd2, A::from_u64(kj[x]), mc.q, mc.qinv) + A::mulmod_any(dd0, pres, mc.q, mc.qinv);
+            acc1[i] += A::mulmod_any(dd2, A::from_u64(kj[kstride + x]), mc.q, mc.qinv) + A::mulmod_any(dd1, pres, mc.q, mc.qinv);
+        }
+    } else if (e <= ep.level) {
         {  // the digit that owns this limb
             const u64* kj = key + (size_t)own * 2 * kstride;
             const u64* yo = ep.D.own.p[b] + (size_t)e * N + off;
@@ -526,8 +554,10 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_mac_kernel(NttArgs arg
     }
 }
 
-template <class A, int IT>
-__global__ __launch_bounds__(NTT_THREADS) void ntt_inv_lo_kernel(NttArgs args, PolyList pl) {
+// MUL (double-precision arithmetic, first pass, source list): the transform's input is the pointwise product of two
+// polynomials (the d2 = a1 (.) b1 of a ciphertext product), formed as the points are loaded: d2 itself is never stored.
+template <class A, int IT, bool MUL = false>
+__global__ __launch_bounds__(NTT_THREADS) __attribute__((amdgpu_waves_per_eu(3, 8))) void ntt_inv_lo_kernel(NttArgs args, PolyList pl) {
     typedef typename A::E E;
     __shared__ E lds0[LDS_PADDED_WORDS];
     __shared__ E lds1[LDS_PADDED_WORDS];
@@ -541,30 +571,49 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_inv_lo_kernel(NttArgs args, P
     const u32 d3 = tid >> 5, x5 = tid & 31, d2 = (tid >> 2) & 7, d0 = tid & 3;
     typedef typename A::TW TW;
     E v[8];
-    ulonglong2 raw[4];
+    ulonglong2 raw[4], raw2[MUL ? 4 : 1];
     TW wa[7], wb[7], wc[7], wd[6];
     load_tw<A, 2>(P.tw, 512 * TA + 2 * tid, wd);
     load_tw<A, 2>(P.tw, 512 * TA + 2 * tid + 1, wd + 3);
     load_tw<A, 3>(P.tw, 64 * TA + 8 * d3 + d2, wc);
+    const size_t moff = ((size_t)pl.spos[tile.a] << args.log_n) + off + 8 * tid;  // MUL: the multiplier's point
     {
         const ulonglong2* in = reinterpret_cast<const ulonglong2*>(P.src + off + 8 * tid);
 #pragma unroll
         for (int j = 0; j < 4; j++) raw[j] = in[j];
+        if constexpr (MUL) {
+            const ulonglong2* in2 = reinterpret_cast<const ulonglong2*>(args.mul_list.p[b0] + moff);
+#pragma unroll
+            for (int j = 0; j < 4; j++) raw2[j] = in2[j];
+        }
     }
 #pragma unroll
     for (int it = 0; it < IT; it++) {
         if ((u32)it >= cnt) break;
         E* buf0 = (it & 1) ? lds1 : lds0;  // three exchanges per item: the buffers swap roles from item to item
         E* buf1 = (it & 1) ? lds0 : lds1;
+        if constexpr (MUL) {
 #pragma unroll
-        for (int j = 0; j < 4; j++) {
-            v[2 * j] = A::load_first(raw[j].x, P.mc, true);
-            v[2 * j + 1] = A::load_first(raw[j].y, P.mc, true);
+            for (int j = 0; j < 4; j++) {
+                v[2 * j] = A::mulmod_any(A::from_u64(raw[j].x), A::from_u64(raw2[j].x), P.mc.q, P.mc.qinv);
+                v[2 * j + 1] = A::mulmod_any(A::from_u64(raw[j].y), A::from_u64(raw2[j].y), P.mc.q, P.mc.qinv);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 4; j++) {
+                v[2 * j] = A::load_first(raw[j].x, P.mc, true);
+                v[2 * j + 1] = A::load_first(raw[j].y, P.mc, true);
+            }
         }
         if (it + 1 < IT && (u32)(it + 1) < cnt) {  // the next item's points, a tile ahead
             const ulonglong2* in = reinterpret_cast<const ulonglong2*>(item_src<A>(args, pl, b0 + it + 1, tile.a) + off + 8 * tid);
 #pragma unroll
             for (int j = 0; j < 4; j++) raw[j] = in[j];
+            if constexpr (MUL) {
+                const ulonglong2* in2 = reinterpret_cast<const ulonglong2*>(args.mul_list.p[b0 + it + 1] + moff);
+#pragma unroll
+                for (int j = 0; j < 4; j++) raw2[j] = in2[j];
+            }
         }
         inv_rows_pre<A, 2>(v, wd, P.mc);
         inv_rows_pre<A, 2>(v + 4, wd + 3, P.mc);
@@ -868,7 +917,13 @@ static void launch_hi_any(u32 log_hi, bool inverse, dim3 grid, hipStream_t st, c
 }
 
 template <class A, int IT>
-static void launch_lo_it(bool inverse, dim3 grid, hipStream_t st, const NttArgs& args, const PolyList& pl) {
+static void launch_lo_it(bool inverse, dim3 grid, hipStream_t st, const NttArgs& args, const PolyList& pl, bool mul = false) {
+    if constexpr (std::is_same<A, ArithF64>::value) {
+        if (inverse && mul) {
+            hipLaunchKernelGGL((ntt_inv_lo_kernel<A, IT, true>), grid, dim3(NTT_THREADS), 0, st, args, pl);
+            return;
+        }
+    }
     if (inverse) hipLaunchKernelGGL((ntt_inv_lo_kernel<A, IT>), grid, dim3(NTT_THREADS), 0, st, args, pl);
     else hipLaunchKernelGGL((ntt_fwd_lo_kernel<A, IT>), grid, dim3(NTT_THREADS), 0, st, args, pl);
 }
@@ -878,9 +933,9 @@ static void launch_lo_div(u32 items, dim3 grid, hipStream_t st, const NttArgs& a
     else hipLaunchKernelGGL((ntt_fwd_lo_div_kernel<A, 1>), grid, dim3(NTT_THREADS), 0, st, args, pl, ep);
 }
 template <class A>
-static void launch_lo(bool inverse, u32 items, dim3 grid, hipStream_t st, const NttArgs& args, const PolyList& pl) {
-    if (items == 2) launch_lo_it<A, 2>(inverse, grid, st, args, pl);
-    else launch_lo_it<A, 1>(inverse, grid, st, args, pl);
+static void launch_lo(bool inverse, u32 items, dim3 grid, hipStream_t st, const NttArgs& args, const PolyList& pl, bool mul = false) {
+    if (items == 2) launch_lo_it<A, 2>(inverse, grid, st, args, pl, mul);
+    else launch_lo_it<A, 1>(inverse, grid, st, args, pl, mul);
 }
 
 constexpr u32 CONV_TARGETS = 4;  // target limbs per workgroup of the converting hi pass
@@ -905,8 +960,10 @@ static void launch_hi_conv(u32 log_hi, u32 ap, dim3 grid, hipStream_t st, const 
 
 static hipError_t launch_ntt_any(const ckks_ctx* c, bool inverse, const u64* src, size_t src_bstride, u64* dst,
                                  size_t dst_bstride, const PolyList& pl, u32 batch, hipStream_t st, const u64* const* src_ptrs,
-                                 const FwdEpilogue* epilogue, const TwF* inv_scale, const ConvPrologue* conv, bool hi_only = false) {
+                                 const FwdEpilogue* epilogue, const TwF* inv_scale, const ConvPrologue* conv, bool hi_only = false,
+                                 const u64* const* mul_ptrs = nullptr) {
     if (pl.n == 0 || batch == 0) return hipSuccess;
+    if (mul_ptrs && (!inverse || !src_ptrs || !ntt_has_modup(c))) return hipErrorInvalidValue;
     if (hi_only && (!conv || epilogue)) return hipErrorInvalidValue;
     if (src_ptrs && batch > KS_MAX_BATCH) return hipErrorInvalidValue;
     if (epilogue && (inverse || !ntt_has_epilogue(c) || batch > 2 * KS_MAX_BATCH)) return hipErrorInvalidValue;
@@ -934,7 +991,10 @@ static hipError_t launch_ntt_any(const ckks_ctx* c, bool inverse, const u64* src
             if (slices % g == 0) { args.lo_group = g; break; }
     }
     args.use_src_list = src_ptrs ? 1 : 0;
-    for (u32 b = 0; b < KS_MAX_BATCH; b++) args.src_list.p[b] = (src_ptrs && b < batch) ? src_ptrs[b] : nullptr;
+    for (u32 b = 0; b < KS_MAX_BATCH; b++) {
+        args.src_list.p[b] = (src_ptrs && b < batch) ? src_ptrs[b] : nullptr;
+        args.mul_list.p[b] = (mul_ptrs && b < batch) ? mul_ptrs[b] : nullptr;
+    }
     args.inv_scale = inv_scale;
     const u32 polys = pl.n * batch;
     const dim3 block(NTT_THREADS);
@@ -987,7 +1047,11 @@ static hipError_t launch_ntt_any(const ckks_ctx* c, bool inverse, const u64* src
         }
     } else {
         args.last = c->log_hi == 0;
-        { ProfScope ps__(c, K_NTT_INV_LO, st, pass_bytes, lo_ops); lo(args, pl); }
+        {
+            ProfScope ps__(c, K_NTT_INV_LO, st, mul_ptrs ? 1.5 * pass_bytes : pass_bytes, lo_ops);
+            if (mul_ptrs) launch_lo<ArithF64>(true, lo_items, grid_lo, st, args, pl, true);
+            else lo(args, pl);
+        }
         if (c->log_hi > 0) { ProfScope ps__(c, K_NTT_INV_HI, st, pass_bytes, hi_ops); hi(second, pd); }
     }
     return hipGetLastError();
@@ -995,8 +1059,9 @@ static hipError_t launch_ntt_any(const ckks_ctx* c, bool inverse, const u64* src
 
 hipError_t launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, size_t src_bstride, u64* dst, size_t dst_bstride,
                       const PolyList& pl, u32 batch, hipStream_t st, const u64* const* src_ptrs, const FwdEpilogue* epilogue,
-                      const TwF* inv_scale) {
-    return launch_ntt_any(c, inverse, src, src_bstride, dst, dst_bstride, pl, batch, st, src_ptrs, epilogue, inv_scale, nullptr);
+                      const TwF* inv_scale, const u64* const* mul_ptrs) {
+    return launch_ntt_any(c, inverse, src, src_bstride, dst, dst_bstride, pl, batch, st, src_ptrs, epilogue, inv_scale, nullptr, false,
+                          mul_ptrs);
 }
 
 hipError_t launch_ntt_modup(const ckks_ctx* c, u32 level, u32 j, const double* y, size_t y_bstride, u64* dst, size_t dst_bstride,
@@ -1013,7 +1078,7 @@ hipError_t launch_ntt_modup(const ckks_ctx* c, u32 level, u32 j, const double* y
 }
 
 hipError_t launch_ntt_lo_mac(const ckks_ctx* c, u32 level, const DigitSrc& digits, const u64* const* keys, const u64* const* add0s,
-                             const u64* const* add1s, u64* const* outs, u32 n, hipStream_t st) {
+                             const u64* const* add1s, u64* const* outs, u32 n, hipStream_t st, const MacProduct* prod) {
     if (!ntt_has_modup(c) || c->log_hi == 0 || n == 0 || n > KS_MAX_BATCH) return hipErrorInvalidValue;
     const u32 E = c->ext_limbs(level), beta = c->live_digits(level);
     NttArgs args = {};
@@ -1039,6 +1104,11 @@ hipError_t launch_ntt_lo_mac(const ckks_ctx* c, u32 level, const DigitSrc& digit
         ep.add1.p[b] = (b < n && add1s) ? add1s[b] : nullptr;
         ep.out.p[b] = b < n ? outs[b] : nullptr;
         if (b < n && !ep.key.p[b]) return hipErrorInvalidValue;
+        ep.a0.p[b] = (prod && b < n) ? prod->a0[b] : nullptr;
+        ep.a1.p[b] = (prod && b < n) ? prod->a1[b] : nullptr;
+        ep.b0.p[b] = (prod && b < n) ? prod->b0[b] : nullptr;
+        ep.b1.p[b] = (prod && b < n) ? prod->b1[b] : nullptr;
+        if (prod && b < n && (!ep.a0.p[b] || !ep.a1.p[b] || !ep.b0.p[b] || !ep.b1.p[b])) return hipErrorInvalidValue;
         n_add += (ep.add0.p[b] ? 1.0 : 0.0) + (ep.add1.p[b] ? 1.0 : 0.0);
         if (b < n && (b == 0 || keys[b] != keys[b - 1])) n_keys += 1.0;
     }
@@ -1047,11 +1117,13 @@ hipError_t launch_ntt_lo_mac(const ckks_ctx* c, u32 level, const DigitSrc& digit
     ep.M = c->M;
     ep.E = E;
     ep.beta = beta;
+    ep.prod = prod ? 1 : 0;
+    ep.pad = 0;
     // digits transformed per batch item: every (digit, position) pair but the digits' own limbs
     const double n_tr = (double)beta * E - (level + 1.0);
     const dim3 grid = args.lo_group ? dim3(args.lo_group, n, slices / args.lo_group) : dim3(n, slices);
     // in: the transformed rows, the own limbs, the addends, the keys (once per distinct key); out: two components
-    ProfScope ps__(c, K_NTT_FWD_LO, st, 8.0 * c->N * (n * (n_tr + (level + 1.0) + 2.0 * E) + n_add * (level + 1.0) + n_keys * 2.0 * beta * E),
+    ProfScope ps__(c, K_NTT_FWD_LO, st, 8.0 * c->N * (n * (n_tr + (prod ? 4.0 : 1.0) * (level + 1.0) + 2.0 * E) + n_add * (level + 1.0) + n_keys * 2.0 * beta * E),
                    0.5 * n * n_tr * c->N * c->log_lo);
     hipLaunchKernelGGL(ntt_fwd_lo_mac_kernel, grid, dim3(NTT_THREADS), 0, st, args, pl, ep);
     return hipGetLastError();
