@@ -1007,8 +1007,10 @@ static hipError_t launch_ntt_any(const ckks_ctx* c, bool inverse, const u64* src
     }
     const dim3 grid(c->N >> CKKS_TILE_LOG, polys);  // hi pass: one workgroup per 2^11 points
     const u32 slices = pl.n << c->log_hi;
-    // batch items per lo-pass workgroup: two share one fetch of the twiddles (four cost too many registers)
-    const u32 lo_items = batch >= 2 ? 2 : 1;
+    // batch items per lo-pass workgroup: two share one fetch of the twiddles (four cost too many registers); the pass that
+    // ends a division takes one (with its epilogue's operands two items leave only two waves per SIMD, which costs more
+    // than the second fetch of the twiddles)
+    const u32 lo_items = (batch >= 2 && !epilogue) ? 2 : 1;
     const u32 lo_wgs = (batch + lo_items - 1) / lo_items;
     const dim3 grid_lo = args.lo_group ? dim3(args.lo_group, lo_wgs, slices / args.lo_group) : dim3(lo_wgs, slices);  // see lo_tile()
     const double lo_ops = 0.5 * polys * c->N * c->log_lo, hi_ops = 0.5 * polys * c->N * c->log_hi;
