@@ -69,6 +69,8 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--no-kernel-timing", action="store_true", help="skip the per-kernel event pass")
     ap.add_argument("--no-microbench", action="store_true", help="skip the rotation and NTT microbenchmarks")
+    ap.add_argument("--rotations-only", action="store_true",
+                    help="only the rotation microbenchmark (64 hoisted + 64 unhoisted rotations, three times each): for profiling runs")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run the library's plain copy kernel on one ciphertext (24 MiB in, 24 MiB out): the known-size "
                          "dispatch that hardware-counter runs are scaled by")
@@ -130,6 +132,33 @@ def cpu_baseline(wl, params, alignment, act_merged):
     }
 
 
+def rotation_microbench(hx, torch, ctx, ct, keys, level, N, ws, result):
+    # rotation microbenchmark (24 limbs + 8 special primes, dnum 3): one ciphertext, 64 distinct offsets, 64 keys in
+    # 64 separate 96 MiB buffers (their contents are clones of the eight seeded keys: only the addresses matter)
+    n_rot_mb = 64
+    from workloads import rotation_offsets
+    mb_offs = rotation_offsets(n_rot_mb, N // 2)
+    base_keys = [k for k in keys if k is not None]
+    mb_keys = [hx.ckks_key_load(ctx, base_keys[i % len(base_keys)].tensor.clone(), hx.ckks_galois_element(ctx, r))
+               for i, r in enumerate(mb_offs)]
+    mb_outs = [hx.empty(2, level + 1, N) for _ in range(n_rot_mb)]
+    for hoisted in (True, False):
+        hx.ckks_rotate_hoisted(ctx, ct, level, mb_offs, mb_keys, hoisted, outs=mb_outs, ws=ws)
+        torch.cuda.synchronize()
+        reps = 3
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            hx.ckks_rotate_hoisted(ctx, ct, level, mb_offs, mb_keys, hoisted, outs=mb_outs, ws=ws)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        name = "hoisted" if hoisted else "unhoisted"
+        rate = n_rot_mb * reps / dt
+        result["rotations_per_s_%s" % name] = rate
+        # compulsory HBM traffic per rotation: key 96 MiB + c0 12 MiB + output 24 MiB (+ 24 MiB input when unhoisted)
+        mib = (96 + 12 + 24) if hoisted else (96 + 24 + 24)
+        result["rotation_%s_effective_GBs" % name] = rate * mib * 2**20 / 1e9
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -176,6 +205,13 @@ def main():
     ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
     torch.cuda.synchronize()
     print("[bench] setup %.1f s, workspace %.2f GiB" % (time.perf_counter() - t_setup, ws_bytes / 2**30), file=sys.stderr, flush=True)
+
+    if args.rotations_only:
+        result = {"workload": "cfg3_rotations (the rotation microbenchmark of the default run)", "single_stream": bool(args.single_stream)}
+        hx.ckks_ctx_set_overlap(ctx, not args.single_stream)
+        rotation_microbench(hx, torch, ctx, ins[0], keys, level, N, ws, result)
+        print(json.dumps(result))
+        return
 
     def step():
         hx.he_conv_batched(ctx, wl.height, wl.width, wl.batch, level, ins, keys, masks, w_res, wl.c_out, outs=conv_out, ws=ws,
@@ -290,31 +326,7 @@ def main():
         return
     # ---- the two microbenchmark shapes, reported next to the headline value ------------------------
     hx.ckks_ctx_set_overlap(ctx, not args.single_stream)
-    # rotation microbenchmark (24 limbs + 8 special primes, dnum 3): one ciphertext, 64 distinct offsets, 64 keys in
-    # 64 separate 96 MiB buffers (their contents are clones of the eight seeded keys: only the addresses matter)
-    n_rot_mb = 64
-    from workloads import rotation_offsets
-    mb_offs = rotation_offsets(n_rot_mb, N // 2)
-    base_keys = [k for k in keys if k is not None]
-    mb_keys = [hx.ckks_key_load(ctx, base_keys[i % len(base_keys)].tensor.clone(), hx.ckks_galois_element(ctx, r))
-               for i, r in enumerate(mb_offs)]
-    mb_outs = [hx.empty(2, level + 1, N) for _ in range(n_rot_mb)]
-    for hoisted in (True, False):
-        hx.ckks_rotate_hoisted(ctx, ins[0], level, mb_offs, mb_keys, hoisted, outs=mb_outs, ws=ws)
-        torch.cuda.synchronize()
-        reps = 3
-        t0 = time.perf_counter()
-        for _ in range(reps):
-            hx.ckks_rotate_hoisted(ctx, ins[0], level, mb_offs, mb_keys, hoisted, outs=mb_outs, ws=ws)
-        torch.cuda.synchronize()
-        dt = time.perf_counter() - t0
-        name = "hoisted" if hoisted else "unhoisted"
-        rate = n_rot_mb * reps / dt
-        result["rotations_per_s_%s" % name] = rate
-        # compulsory HBM traffic per rotation: key 96 MiB + c0 12 MiB + output 24 MiB (+ 24 MiB input when unhoisted)
-        mib = (96 + 12 + 24) if hoisted else (96 + 24 + 24)
-        result["rotation_%s_effective_GBs" % name] = rate * mib * 2**20 / 1e9
-    del mb_keys, mb_outs
+    rotation_microbench(hx, torch, ctx, ins[0], keys, level, N, ws, result)
     # accumulator merge (the optimised pipeline's block-group transition): 4 intermediate ciphertexts with 8192
     # occupied slots each -> one full ciphertext, at the level the block slice leaves its outputs on
     acc_level, acc_g, acc_sts = level - 5, 4, 8192
