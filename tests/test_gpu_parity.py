@@ -155,6 +155,36 @@ def test_ctct_mul_relin_matches_oracle(ks_setup, level):
     assert np.array_equal(hx.to_host(sq), orc.ctct_mul_relin(a, a, rlk, level))
 
 
+@pytest.mark.parametrize("log_n,num_q,num_p,dnum,bits", [(12, 8, 2, 4, 50), (12, 6, 3, 2, 50), (12, 5, 5, 1, 50), (13, 9, 3, 3, 50),
+                                                       (12, 8, 2, 4, 56), (11, 6, 3, 2, 50)])
+def test_key_switch_paths_with_other_digit_shapes(log_n, num_q, num_p, dnum, bits):
+    """Four digits of two limbs, two of three, a single digit, three full digits of three; rings with one and two first-pass
+    stages and the single-pass ring; both arithmetic paths: key switch, relinearised product and both rotation modes at the
+    top level, at a level with a ragged last digit and at level 0."""
+    p = make_params(log_n, num_q, num_p, dnum, bits=bits)
+    orc, ctx = both(p)
+    s, s_ntt = orc.gen_secret(81)
+    rlk = orc.gen_relin_key(s_ntt, 82)
+    d_rlk = hx.ckks_key_load(ctx, hx.from_host(rlk), 0)
+    offs = [1, -3, 0, 37]
+    keys = [orc.gen_rotation_key(s, s_ntt, r, 83 + i) if r else None for i, r in enumerate(offs)]
+    dkeys = [hx.ckks_key_load(ctx, hx.from_host(k), hx.ckks_galois_element(ctx, r)) if k is not None else None
+             for k, r in zip(keys, offs)]
+    alpha = -(-num_q // dnum)
+    for level in sorted({num_q - 1, max(0, num_q - 1 - alpha // 2 - 1), 0}, reverse=True):
+        rng = np.random.default_rng(90 + level)
+        c = rand_poly(rng, p.moduli[:level + 1], orc.N)
+        assert np.array_equal(hx.to_host(hx.ckks_keyswitch(ctx, hx.from_host(c), level, d_rlk)), orc.keyswitch(c, rlk, level)), level
+        a, b = rand_ct(rng, p.moduli, level, orc.N), rand_ct(rng, p.moduli, level, orc.N)
+        got = hx.ckks_ctct_mul_relin(ctx, hx.from_host(a), hx.from_host(b), level, d_rlk)
+        assert np.array_equal(hx.to_host(got), orc.ctct_mul_relin(a, b, rlk, level)), level
+        for hoisted in (True, False):
+            outs = hx.ckks_rotate_hoisted(ctx, hx.from_host(a), level, offs, dkeys, hoisted)
+            want = orc.rotate_many(a, level, offs, keys, hoisted)
+            for r, o, w in zip(offs, outs, want):
+                assert np.array_equal(hx.to_host(o), w), (level, hoisted, r)
+
+
 # ----------------------------------------------------------------------------------- convolution
 def conv_case(name, level=None, bits=50, four_keys=False, deferred=False, merged=False, narrow=False):
     wl = CONFIGS[name]
