@@ -157,7 +157,9 @@ FwdEpilogue moddown_epilogue(const ckks_ctx* c, u32 level, bool merged, const u6
     ep.E = c->ext_limbs(level);
     ep.n_out = merged ? level : level + 1;
     ep.num_q = c->num_q;
-    ep.pad = 0;
+    ep.use_vl = 0;
+    ep.v_cstride = 0;
+    for (u32 r = 0; r < KS_MAX_BATCH; r++) ep.vl.p[r] = nullptr;
     for (u32 r = 0; r < KS_MAX_BATCH; r++) ep.B.it[r] = r < n ? items[r] : FinalItem{nullptr, nullptr, nullptr, nullptr, 1, 0};
     return ep;
 }
@@ -218,6 +220,26 @@ int run_rescale(const ckks_ctx* c, u32 level, const u64* const* cts, size_t ct_c
     for (u32 b = 0; b < n; b++) {
         last[2 * b] = cts[b] + (size_t)level * N;
         last[2 * b + 1] = cts[b] + ct_cstride + (size_t)level * N;
+    }
+    if (ntt_has_modup(c)) {
+        // the rescale as a division by one dropped limb through the fused passes: the inverse transform leaves centred doubles,
+        // the forward transform reduces them modulo each remaining limb as it loads and applies (c_i - w_i) q_level^-1 as it stores
+        HIP_TRY(launch_ntt(c, true, nullptr, 0, r, 1, range_list(0, 1, level), 2 * n, st, last, nullptr, c->d_rescale_prep_f));
+        FwdEpilogue ep;
+        ep.v = nullptr;
+        ep.cinv = c->d_rescale_ep + (size_t)level * 2 * c->num_q;
+        ep.mci = c->d_mc;
+        ep.E = 0;
+        ep.n_out = level;
+        ep.num_q = c->num_q;
+        ep.use_vl = 1;
+        ep.v_cstride = ct_cstride;
+        for (u32 b = 0; b < KS_MAX_BATCH; b++) {
+            ep.vl.p[b] = b < n ? cts[b] : nullptr;
+            ep.B.it[b] = b < n ? FinalItem{nullptr, nullptr, nullptr, outs[b], 1, 0} : FinalItem{nullptr, nullptr, nullptr, nullptr, 1, 0};
+        }
+        HIP_TRY(launch_ntt_rescale(c, level, (const double*)r, w, 2 * n, st, &ep));
+        return CKKS_OK;
     }
     HIP_TRY(launch_ntt(c, true, nullptr, 0, r, 1, range_list(0, 1, level), 2 * n, st, last));
     HIP_TRY(launch_rescale_conv(c, level, r, w, 2 * n, st));

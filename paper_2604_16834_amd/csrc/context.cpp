@@ -74,6 +74,9 @@ extern "C" void ckks_ctx_destroy(ckks_ctx* c) {
     (void)hipFree(c->d_moddown_f);
     (void)hipFree(c->d_moddown_rs_f);
     (void)hipFree(c->d_moddown_prep_f);
+    (void)hipFree(c->d_rescale_prep_f);
+    (void)hipFree(c->d_rescale_conv_f);
+    (void)hipFree(c->d_rescale_ep);
     (void)hipFree(c->d_moddown_rs_prep_f);
     (void)hipFree(c->d_rescale);
     if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
@@ -276,7 +279,7 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
         }
     }
     // the conversion constants as doubles (value, value / target modulus) for the double-precision conversions
-    std::vector<TwF> modup_f, modup_prep_f, moddown_f, moddown_rs_f, moddown_prep_f, moddown_rs_prep_f;
+    std::vector<TwF> modup_f, modup_prep_f, moddown_f, moddown_rs_f, moddown_prep_f, moddown_rs_prep_f, rescale_prep_f, rescale_conv_f;
     if (c->dnum && c->ntt_f64) {
         const u32 nq = c->num_q;
         modup_f.assign((size_t)nq * c->dnum * M * c->alpha_pad, TwF{0.0, 0.0});
@@ -314,6 +317,11 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
             const double w = (double)h_mulmod(inv, c->mc[m].n_inv, q);
             return TwF{w, w / (double)q};
         };
+        // the rescale as a one-limb conversion: the inverse transform scales by 1/N only, the conversion constant is 1
+        rescale_prep_f.assign(M, TwF{0.0, 0.0});
+        for (u32 m = 0; m < M; m++) rescale_prep_f[m] = TwF{(double)c->mc[m].n_inv, (double)c->mc[m].n_inv / (double)c->mod[m]};
+        rescale_conv_f.assign((size_t)nq * 4, TwF{0.0, 0.0});
+        for (u32 i = 0; i < nq; i++) rescale_conv_f[(size_t)i * 4] = TwF{1.0, 1.0 / (double)c->mod[i]};
         moddown_prep_f.assign(M, TwF{0.0, 0.0});
         for (u32 a = 0; a < c->num_p; a++) moddown_prep_f[nq + a] = prep(moddown[a], nq + a);
         moddown_rs_prep_f.assign((size_t)nq * M, TwF{0.0, 0.0});
@@ -342,8 +350,19 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
             t[0] = inv; t[1] = h_shoup(inv, qi); t[2] = ql;
         }
 
+    // the rescale constants once more, in the layout the transforms' division epilogue reads
+    std::vector<u64> resc_ep((size_t)c->num_q * 2 * c->num_q, 0);
+    for (u32 l = 0; l < c->num_q; l++)
+        for (u32 i = 0; i < l; i++) {
+            resc_ep[((size_t)l * 2 + 0) * c->num_q + i] = resc[((size_t)l * c->num_q + i) * 3 + 0];
+            resc_ep[((size_t)l * 2 + 1) * c->num_q + i] = resc[((size_t)l * c->num_q + i) * 3 + 1];
+        }
+
     hipError_t e = hipSuccess;
     if (e == hipSuccess) e = upload(c->mc, &c->d_mc);
+    if (e == hipSuccess) e = upload(resc_ep, &c->d_rescale_ep);
+    if (e == hipSuccess) e = upload(rescale_prep_f, &c->d_rescale_prep_f);
+    if (e == hipSuccess) e = upload(rescale_conv_f, &c->d_rescale_conv_f);
     if (e == hipSuccess) e = upload(tw, &c->d_tw);
     if (e == hipSuccess) e = upload(itw, &c->d_itw);
     if (e == hipSuccess) e = upload(twf, &c->d_twf);

@@ -102,7 +102,10 @@ struct FwdEpilogue {
     const u64* v;         // [batch][E][N]
     const u64* cinv;      // the multiplier per limb, its Shoup companion at cinv[num_q + i]
     const ModConst* mci;  // integer constants per modulus
-    u32 E, n_out, num_q, pad;
+    u32 E, n_out, num_q;
+    u32 use_vl;           // v is given per ciphertext instead: item 2r + comp reads vl.p[r] + comp * v_cstride (the rescale)
+    PtrList8 vl;
+    size_t v_cstride;
     FinalBatch B;
 };
 
@@ -139,6 +142,9 @@ struct ckks_ctx {
     TwF* d_modup_prep_f = nullptr;    // [level][num_q]: N^-1 (Q_j/q_i)^-1 mod q_i, what the inverse transform in front of ModUp scales by
     TwF* d_moddown_f = nullptr;       // [num_q][k_pad]
     TwF* d_moddown_rs_f = nullptr;    // [level][num_q][k2_pad]
+    TwF* d_rescale_prep_f = nullptr;     // [M], by modulus: N^-1 mod q_m (the inverse transform in front of a fused rescale)
+    TwF* d_rescale_conv_f = nullptr;     // [num_q][4]: (1, 1 / q_i), 0, 0, 0: the "conversion" of the one dropped limb
+    u64* d_rescale_ep = nullptr;         // [level][2][num_q]: q_level^-1 mod q_i and its Shoup companion, as FwdEpilogue.cinv
     TwF* d_moddown_prep_f = nullptr;     // [M], by modulus: N^-1 (P/p_a)^-1 mod p_a at the special primes (zero elsewhere)
     TwF* d_moddown_rs_prep_f = nullptr;  // [level][M], by modulus: N^-1 (P q_l / m)^-1 mod m for m in {q_l, p_0..p_{k-1}}
     const TwF* modup_table_f(u32 level, u32 j) const { return d_modup_f + ((size_t)level * dnum + j) * M * alpha_pad; }
@@ -211,6 +217,10 @@ inline bool ntt_has_modup(const ckks_ctx* c) { return c->ntt_f64 && c->log_n > C
 // centred doubles by launch_ntt with the moddown prep table), dst the converted dropped part ([n_out][N] per polynomial,
 // NTT form), epilogue what the second pass does with it.  merged: the dropped set is {q_level, p_0..p_{k-1}}.
 hipError_t launch_ntt_moddown(const ckks_ctx* c, u32 level, bool merged, const double* y, u64* dst, u32 batch, hipStream_t st,
+                              const FwdEpilogue* epilogue);
+// The same for the rescale: y [batch][N] is the dropped limb `level` of every component (centred doubles, from launch_ntt
+// with d_rescale_prep_f), dst [batch][level][N] scratch, epilogue the subtraction and the multiplication by q_level^-1.
+hipError_t launch_ntt_rescale(const ckks_ctx* c, u32 level, const double* y, u64* dst, u32 batch, hipStream_t st,
                               const FwdEpilogue* epilogue);
 // hi_only: stop after the converting hi pass; launch_ntt_lo_mac then runs the lo passes of all digits and multiplies the
 // results by the switching keys (keys[b]: [dnum][2][M][N], one per batch item) as they come out, adding P * add0s[b] /

@@ -338,7 +338,9 @@ __device__ __forceinline__ void fwd_lo_body(const NttArgs& args, const PolyList&
         for (int j = 0; j < 8; j++) v[j] = buf0[LDS_PAD(8 * tid + j)];
         u64 vv[8];
         if (EPI) {  // what the results are subtracted from: requested now, needed after the last round
-            const u64* vrow = ep.v + (((size_t)(b0 + it) * ep.E + pl.dpos[tile.a]) << args.log_n) + off;
+            const u32 bv = b0 + it;
+            const u64* vrow = (ep.use_vl ? ep.vl.p[bv >> 1] + (bv & 1) * ep.v_cstride + ((size_t)pl.dpos[tile.a] << args.log_n)
+                                         : ep.v + (((size_t)bv * ep.E + pl.dpos[tile.a]) << args.log_n)) + off;
 #pragma unroll
             for (int j = 0; j < 8; j++) vv[j] = vrow[tid + 256 * j];
         }
@@ -1077,6 +1079,23 @@ hipError_t launch_ntt_modup(const ckks_ctx* c, u32 level, u32 j, const double* y
     cp.ap = c->alpha_pad;
     cp.pad = 0;
     return launch_ntt_any(c, false, dst, dst_bstride, dst, dst_bstride, pl, batch, st, nullptr, nullptr, nullptr, &cp, hi_only);
+}
+
+hipError_t launch_ntt_rescale(const ckks_ctx* c, u32 level, const double* y, u64* dst, u32 batch, hipStream_t st,
+                              const FwdEpilogue* epilogue) {
+    if (level == 0 || !c->d_rescale_conv_f) return hipErrorInvalidValue;
+    ConvPrologue cp;
+    cp.y = y;
+    cp.y_bstride = c->N;  // one limb per batch item
+    cp.convf = c->d_rescale_conv_f;
+    cp.lo = 0;
+    cp.nd = 1;
+    cp.ap = 4;
+    cp.pad = 0;
+    PolyList pl;
+    for (u32 a = 0; a < CKKS_MAX_MODULI; a++) pl.spos[a] = pl.dpos[a] = pl.mod[a] = (unsigned char)(a < level ? a : 0);
+    pl.n = level;
+    return launch_ntt_any(c, false, dst, level, dst, level, pl, batch, st, nullptr, epilogue, nullptr, &cp);
 }
 
 hipError_t launch_ntt_lo_mac(const ckks_ctx* c, u32 level, const DigitSrc& digits, const u64* const* keys, const u64* const* add0s,
