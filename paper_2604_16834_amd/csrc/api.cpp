@@ -286,8 +286,18 @@ int run_ctct(const ckks_ctx* c, u32 level, const u64* const* a, size_t a_cstride
 // one division by P*q_level: the tensor product's d0, d1 (plus the addend) enter the extended basis as P times
 // themselves inside the inner-product kernel.  addend (optional): n ciphertexts [2][level+1][N], item stride
 // add_bstride.  outs[b] = [2][level][N].
+// lin (optional, contexts with the fused inner product only, instead of addend): the addend is ka * x + kb * y, formed on the fly.
+struct LinAddend {
+    const u64* const* x;
+    size_t x_cstride;
+    const u64* ka;
+    const u64* const* y;
+    size_t y_cstride;
+    const u64* kb;
+};
 int run_ctct_merged(const ckks_ctx* c, u32 level, const u64* const* a, size_t a_cstride, const u64* const* b, size_t b_cstride,
-                    const u64* addend, size_t add_bstride, const u64* d_rlk, u64* const* outs, u32 n, Arena ar, hipStream_t st) {
+                    const u64* addend, size_t add_bstride, const u64* d_rlk, u64* const* outs, u32 n, Arena ar, hipStream_t st,
+                    const LinAddend* lin = nullptr) {
     const size_t N = c->N, L1 = level + 1;
     u64* d0 = ar.take(n * L1 * N);
     u64* d1 = ar.take(n * L1 * N);
@@ -295,6 +305,7 @@ int run_ctct_merged(const ckks_ctx* c, u32 level, const u64* const* a, size_t a_
     KsWs ws;
     if (!carve_ks(c, level, n, n, ar, ws)) return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for ct-ct multiply");
     const bool mac = ntt_has_modup(c);  // the inner product inside the forward transforms' second pass
+    if (lin && (!mac || addend)) return set_err(c, CKKS_ERR_INVALID_ARG, "internal: linear addend without the fused inner product");
     const u64 *d2s[CT_BATCH], *add0[CT_BATCH], *add1[CT_BATCH];
     u64* vs[CT_BATCH];
     FinalItem items[CT_BATCH];
@@ -313,7 +324,15 @@ int run_ctct_merged(const ckks_ctx* c, u32 level, const u64* const* a, size_t a_
         }
         int rc = run_modup(c, level, a1, n, ws, st, true, b1);
         if (rc) return rc;
-        const MacProduct prod = {a, a1, b, b1};
+        MacProduct prod = {a, a1, b, b1};
+        if (lin) {
+            prod.lin_x = lin->x;
+            prod.x_cstride = lin->x_cstride;
+            prod.ka = lin->ka;
+            prod.lin_y = lin->y;
+            prod.y_cstride = lin->y_cstride;
+            prod.kb = lin->kb;
+        }
         HIP_TRY(launch_ntt_lo_mac(c, level, dsrc(c, ws, 0), keys, addend ? add0 : nullptr, addend ? add1 : nullptr, vs, n, st, &prod));
         return run_moddown(c, level, ws, n, items, st, true);
     }
@@ -1475,6 +1494,11 @@ int he_poly_act_deg7(const ckks_ctx* c, const uint64_t* const* h_d_x, uint32_t n
             // y = Rescale(x4 * B + (k1 * x + k3 * x3)): the linear part rides along as the product's addend
             residues(h_k[0], l3, ka);
             residues(h_k[1], l3, kb);
+            if (ntt_has_modup(c)) {  // the linear part is formed inside the product's fused inner product
+                const LinAddend lin = {px, xs, ka, px3, x3s, kb};
+                if ((rc = run_ctct_merged(c, l3, px4, x3s, pB, Bs, nullptr, 0, rlk->d_key, oout, n, ar.rest(), st, &lin))) return join(rc);
+                continue;
+            }
             if (hipError_t he_ = (launch_lincomb2(c, l3, ptr_list(px, n), xs, ka, ptr_list(px3, n), x3s, kb, nullptr, 0, tmp, 2 * Bs, n, st)); he_ != hipSuccess) return join(set_hip_err(c, he_));
             if ((rc = run_ctct_merged(c, l3, px4, x3s, pB, Bs, tmp, 2 * Bs, rlk->d_key, oout, n, ar.rest(), st))) return join(rc);
             continue;

@@ -231,11 +231,18 @@ hipError_t launch_ntt_modup(const ckks_ctx* c, u32 level, u32 j, const double* y
 // transform took it as a product, launch_ntt with mul_ptrs): the term of the digits' own limbs and the addends
 // d0 = a0 (.) b0 + add0, d1 = a0 (.) b1 + a1 (.) b0 + add1 are formed from the operands (host arrays of n device pointers,
 // [level+1][N] each).
+// lin (optional): the product's addend is the linear combination ka * x + kb * y of two more ciphertexts (component
+// strides x_cstride, y_cstride; ka, kb: one residue per q-limb), formed on the fly as well; add0s / add1s must then be null.
 struct MacProduct {
     const u64* const* a0;
     const u64* const* a1;
     const u64* const* b0;
     const u64* const* b1;
+    const u64* const* lin_x = nullptr;
+    const u64* const* lin_y = nullptr;
+    size_t x_cstride = 0, y_cstride = 0;
+    const u64* ka = nullptr;
+    const u64* kb = nullptr;
 };
 hipError_t launch_ntt_lo_mac(const ckks_ctx* c, u32 level, const DigitSrc& digits, const u64* const* keys, const u64* const* add0s,
                              const u64* const* add1s, u64* const* outs, u32 n, hipStream_t st, const MacProduct* prod = nullptr);

@@ -411,7 +411,11 @@ struct MacEpilogue {
     // nowhere in evaluation form: the own-limb term is formed from a1, b1 ([level+1][N] each, per batch item), and the
     // addends are d0 = a0 (.) b0 + add0 and d1 = a0 (.) b1 + a1 (.) b0 + add1 (D.own is not read)
     PtrList8 a0, a1, b0, b1;
-    u32 prod, pad;
+    u32 prod, lin;
+    // lin != 0 (with prod): the addends are ka * x + kb * y of two more ciphertexts (component 1 at + x_cstride, y_cstride)
+    PtrList8 lx, ly;
+    size_t x_cstride, y_cstride;
+    u64 ka[CKKS_MAX_MODULI], kb[CKKS_MAX_MODULI];
 };
 
 __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_mac_kernel(NttArgs args, PolyList pl, MacEpilogue ep) {
@@ -510,6 +514,9 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_mac_kernel(NttArgs arg
         const u64* c0 = ep.add0.p[b];
         const u64* c1 = ep.add1.p[b];
         const double pres = mc.q - A::from_u64(ep.negp[e]);  // P mod q_e
+        const u64* lx = ep.lin ? ep.lx.p[b] + po : nullptr;
+        const u64* ly = ep.lin ? ep.ly.p[b] + po : nullptr;
+        const double ka = ep.lin ? A::from_u64(ep.ka[e]) : 0.0, kb = ep.lin ? A::from_u64(ep.kb[e]) : 0.0;
 #pragma unroll
         for (int i = 0; i < 8; i++) {
             const u32 x = tid + 256 * i;
@@ -519,6 +526,11 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_mac_kernel(NttArgs arg
             double dd1 = A::mulmod_any(A0, B1, mc.q, mc.qinv) + A::mulmod_any(A1, B0, mc.q, mc.qinv);
             if (c0) dd0 += A::from_u64(c0[po + x]);
             if (c1) dd1 += A::from_u64(c1[po + x]);
+            if (lx) {  // at most 0.57 q more per term: both sums stay below 2^52
+                dd0 += A::mulmod_any(A::from_u64(lx[x]), ka, mc.q, mc.qinv) + A::mulmod_any(A::from_u64(ly[x]), kb, mc.q, mc.qinv);
+                dd1 += A::mulmod_any(A::from_u64(lx[ep.x_cstride + x]), ka, mc.q, mc.qinv) +
+                       A::mulmod_any(A::from_u64(ly[ep.y_cstride + x]), kb, mc.q, mc.qinv);
+            }
             dd0 = A::reduce(dd0, mc);  // back below q / 2 + 1 as multiplicands
             dd1 = A::reduce(dd1, mc);
             acc0[i] += A::mulmod_any(dd2, A::from_u64(kj[x]), mc.q, mc.qinv) + A::mulmod_any(dd0, pres, mc.q, mc.qinv);
@@ -1139,11 +1151,24 @@ hipError_t launch_ntt_lo_mac(const ckks_ctx* c, u32 level, const DigitSrc& digit
     ep.E = E;
     ep.beta = beta;
     ep.prod = prod ? 1 : 0;
-    ep.pad = 0;
+    ep.lin = (prod && prod->lin_x) ? 1 : 0;
+    if (ep.lin && (add0s || add1s || !prod->lin_y || !prod->ka || !prod->kb)) return hipErrorInvalidValue;
+    ep.x_cstride = ep.lin ? prod->x_cstride : 0;
+    ep.y_cstride = ep.lin ? prod->y_cstride : 0;
+    for (u32 b = 0; b < KS_MAX_BATCH; b++) {
+        ep.lx.p[b] = (ep.lin && b < n) ? prod->lin_x[b] : nullptr;
+        ep.ly.p[b] = (ep.lin && b < n) ? prod->lin_y[b] : nullptr;
+        if (ep.lin && b < n && (!ep.lx.p[b] || !ep.ly.p[b])) return hipErrorInvalidValue;
+    }
+    for (u32 i = 0; i < CKKS_MAX_MODULI; i++) {
+        ep.ka[i] = (ep.lin && i <= level) ? prod->ka[i] : 0;
+        ep.kb[i] = (ep.lin && i <= level) ? prod->kb[i] : 0;
+    }
     // digits transformed per batch item: every (digit, position) pair but the digits' own limbs
     const double n_tr = (double)beta * E - (level + 1.0);
     const dim3 grid = args.lo_group ? dim3(args.lo_group, n, slices / args.lo_group) : dim3(n, slices);
     // in: the transformed rows, the own limbs, the addends, the keys (once per distinct key); out: two components
+    if (ep.lin) n_add = 4.0 * n;  // two components of two ciphertexts
     ProfScope ps__(c, K_NTT_FWD_LO, st, 8.0 * c->N * (n * (n_tr + (prod ? 4.0 : 1.0) * (level + 1.0) + 2.0 * E) + n_add * (level + 1.0) + n_keys * 2.0 * beta * E),
                    0.5 * n * n_tr * c->N * c->log_lo);
     hipLaunchKernelGGL(ntt_fwd_lo_mac_kernel, grid, dim3(NTT_THREADS), 0, st, args, pl, ep);
