@@ -158,8 +158,8 @@ FwdEpilogue moddown_epilogue(const ckks_ctx* c, u32 level, bool merged, const u6
     ep.n_out = merged ? level : level + 1;
     ep.num_q = c->num_q;
     ep.use_vl = 0;
-    ep.v_cstride = 0;
-    for (u32 r = 0; r < KS_MAX_BATCH; r++) ep.vl.p[r] = nullptr;
+    ep.v_cstride = ep.v2_cstride = 0;
+    for (u32 r = 0; r < KS_MAX_BATCH; r++) ep.vl.p[r] = ep.vl2.p[r] = nullptr;
     for (u32 r = 0; r < KS_MAX_BATCH; r++) ep.B.it[r] = r < n ? items[r] : FinalItem{nullptr, nullptr, nullptr, nullptr, 1, 0};
     return ep;
 }
@@ -234,7 +234,9 @@ int run_rescale(const ckks_ctx* c, u32 level, const u64* const* cts, size_t ct_c
         ep.num_q = c->num_q;
         ep.use_vl = 1;
         ep.v_cstride = ct_cstride;
+        ep.v2_cstride = 0;
         for (u32 b = 0; b < KS_MAX_BATCH; b++) {
+            ep.vl2.p[b] = nullptr;
             ep.vl.p[b] = b < n ? cts[b] : nullptr;
             ep.B.it[b] = b < n ? FinalItem{nullptr, nullptr, nullptr, outs[b], 1, 0} : FinalItem{nullptr, nullptr, nullptr, nullptr, 1, 0};
         }
@@ -245,6 +247,47 @@ int run_rescale(const ckks_ctx* c, u32 level, const u64* const* cts, size_t ct_c
     HIP_TRY(launch_rescale_conv(c, level, r, w, 2 * n, st));
     HIP_TRY(launch_ntt(c, false, w, level, w, level, range_list(0, level, 0), 2 * n, st));
     HIP_TRY(launch_rescale_final(c, level, ptr_list(cts, n), ct_cstride, w, out_list(outs, n), n, st));
+    return CKKS_OK;
+}
+
+// The same for Rescale(ka * x[b] + kb * y[b]) (double-precision contexts with the fused passes): the linear combination is
+// formed where it is read, in the inverse transform of the dropped limb and in the division's last step.
+int run_rescale_lin(const ckks_ctx* c, u32 level, const u64* const* xs, size_t x_cstride, const u64* ka, const u64* const* ys,
+                    size_t y_cstride, const u64* kb, u64* const* outs, u32 n, Arena ar, hipStream_t st) {
+    if (!ntt_has_modup(c)) return set_err(c, CKKS_ERR_INVALID_ARG, "internal: fused rescale of a linear combination");
+    const size_t N = c->N;
+    u64* r = ar.take(2 * (size_t)n * N);
+    u64* w = ar.take(2 * (size_t)n * level * N);
+    if (!ar.ok()) return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for rescale");
+    const u64 *last[KS_MAX_BATCH], *last2[KS_MAX_BATCH];
+    for (u32 b = 0; b < n; b++) {
+        last[2 * b] = xs[b] + (size_t)level * N;
+        last[2 * b + 1] = xs[b] + x_cstride + (size_t)level * N;
+        last2[2 * b] = ys[b] + (size_t)level * N;
+        last2[2 * b + 1] = ys[b] + y_cstride + (size_t)level * N;
+    }
+    const u64 lin_k[2] = {ka[level], kb[level]};
+    HIP_TRY(launch_ntt(c, true, nullptr, 0, r, 1, range_list(0, 1, level), 2 * n, st, last, nullptr, c->d_rescale_prep_f, last2, lin_k));
+    FwdEpilogue ep;
+    ep.v = nullptr;
+    ep.cinv = c->d_rescale_ep + (size_t)level * 2 * c->num_q;
+    ep.mci = c->d_mc;
+    ep.E = 0;
+    ep.n_out = level;
+    ep.num_q = c->num_q;
+    ep.use_vl = 2;
+    ep.v_cstride = x_cstride;
+    ep.v2_cstride = y_cstride;
+    for (u32 b = 0; b < KS_MAX_BATCH; b++) {
+        ep.vl.p[b] = b < n ? xs[b] : nullptr;
+        ep.vl2.p[b] = b < n ? ys[b] : nullptr;
+        ep.B.it[b] = b < n ? FinalItem{nullptr, nullptr, nullptr, outs[b], 1, 0} : FinalItem{nullptr, nullptr, nullptr, nullptr, 1, 0};
+    }
+    for (u32 i = 0; i < CKKS_MAX_MODULI; i++) {
+        ep.ka[i] = i < level ? ka[i] : 0;
+        ep.kb[i] = i < level ? kb[i] : 0;
+    }
+    HIP_TRY(launch_ntt_rescale(c, level, (const double*)r, w, 2 * n, st, &ep));
     return CKKS_OK;
 }
 
@@ -1488,9 +1531,13 @@ int he_poly_act_deg7(const ckks_ctx* c, const uint64_t* const* h_d_x, uint32_t n
             if ((rc = run_ctct_merged(c, l1, px2, x2s, px2, x2s, nullptr, 0, rlk->d_key, ox4, n, ar.rest(), st))) return join(rc);
             residues(h_k[2], l2, ka);
             residues(h_k[3], l2, kb);
-            tmp_at(x3s);
-            if (hipError_t he_ = (launch_lincomb2(c, l2, ptr_list(px, n), xs, ka, ptr_list(px3, n), x3s, kb, nullptr, 0, tmp, 2 * x3s, n, st)); he_ != hipSuccess) return join(set_hip_err(c, he_));
-            if ((rc = run_rescale(c, l2, ptmp, x3s, oB, n, ar.rest(), st))) return join(rc);
+            if (ntt_has_modup(c)) {  // B = Rescale(k5 * x + k7 * x3) without storing the linear combination
+                if ((rc = run_rescale_lin(c, l2, px, xs, ka, px3, x3s, kb, oB, n, ar.rest(), st))) return join(rc);
+            } else {
+                tmp_at(x3s);
+                if (hipError_t he_ = (launch_lincomb2(c, l2, ptr_list(px, n), xs, ka, ptr_list(px3, n), x3s, kb, nullptr, 0, tmp, 2 * x3s, n, st)); he_ != hipSuccess) return join(set_hip_err(c, he_));
+                if ((rc = run_rescale(c, l2, ptmp, x3s, oB, n, ar.rest(), st))) return join(rc);
+            }
             // y = Rescale(x4 * B + (k1 * x + k3 * x3)): the linear part rides along as the product's addend
             residues(h_k[0], l3, ka);
             residues(h_k[1], l3, kb);

@@ -106,6 +106,11 @@ struct FwdEpilogue {
     u32 use_vl;           // v is given per ciphertext instead: item 2r + comp reads vl.p[r] + comp * v_cstride (the rescale)
     PtrList8 vl;
     size_t v_cstride;
+    // use_vl == 2 (double-precision arithmetic): v = ka * vl + kb * vl2, a linear combination of two ciphertexts with one
+    // scalar residue per limb, formed as it is read
+    PtrList8 vl2;
+    size_t v2_cstride;
+    u64 ka[CKKS_MAX_MODULI], kb[CKKS_MAX_MODULI];
     FinalBatch B;
 };
 
@@ -207,7 +212,10 @@ struct ProfScope {
 // array of `batch` <= KS_MAX_BATCH device pointers) and writes dst + b*dst_bstride*N
 hipError_t launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, size_t src_bstride, u64* dst,
                       size_t dst_bstride, const PolyList& pl, u32 batch, hipStream_t st, const u64* const* src_ptrs = nullptr,
-                      const FwdEpilogue* epilogue = nullptr, const TwF* inv_scale = nullptr, const u64* const* mul_ptrs = nullptr);
+                      const FwdEpilogue* epilogue = nullptr, const TwF* inv_scale = nullptr, const u64* const* mul_ptrs = nullptr,
+                      const u64* lin_k = nullptr);
+// mul_ptrs (inverse, with src_ptrs, double-precision arithmetic): batch item b is src_ptrs[b] (.) mul_ptrs[b], formed on load;
+// with lin_k = {ka, kb} (one limb only) it is ka * src_ptrs[b] + kb * mul_ptrs[b] instead.
 // ModUp fused into transforms (contexts with ntt_f64 and the two-pass transform): the inverse transform of the polynomial
 // scales the limb with modulus index m by inv_scale[m] instead of 1/N and stores the CENTRED residue as a double (launch_ntt with inv_scale);
 // launch_ntt_modup then evaluates the basis conversion of digit j, y [batch][level+1][N] doubles -> the pl.n target limbs

@@ -207,6 +207,8 @@ struct NttArgs {
     u32 use_src_list;    // batch item b reads src_list.p[b] instead of src + b*src_bstride*N
     PtrList8 src_list;
     PtrList8 mul_list;     // inverse, first pass, product variant: batch item b is src_list.p[b] (.) mul_list.p[b]
+    u64 lin_ka, lin_kb;    // use_lin: ... is lin_ka * src_list.p[b] + lin_kb * mul_list.p[b] instead (one limb per item)
+    u32 use_lin, pad2;
     const TwF* inv_scale;  // inverse, last pass (double-precision arithmetic): the limb of modulus m is scaled by inv_scale[m]
                            // instead of 1/N and stored as the centred residue in a double (the form ModUp's conversion reads)
 };
@@ -336,13 +338,20 @@ __device__ __forceinline__ void fwd_lo_body(const NttArgs& args, const PolyList&
         __syncthreads();
 #pragma unroll
         for (int j = 0; j < 8; j++) v[j] = buf0[LDS_PAD(8 * tid + j)];
-        u64 vv[8];
+        u64 vv[8], vv2[8];
         if (EPI) {  // what the results are subtracted from: requested now, needed after the last round
             const u32 bv = b0 + it;
             const u64* vrow = (ep.use_vl ? ep.vl.p[bv >> 1] + (bv & 1) * ep.v_cstride + ((size_t)pl.dpos[tile.a] << args.log_n)
                                          : ep.v + (((size_t)bv * ep.E + pl.dpos[tile.a]) << args.log_n)) + off;
 #pragma unroll
             for (int j = 0; j < 8; j++) vv[j] = vrow[tid + 256 * j];
+            if constexpr (std::is_same<A, ArithF64>::value) {
+                if (ep.use_vl == 2) {
+                    const u64* vrow2 = ep.vl2.p[bv >> 1] + (bv & 1) * ep.v2_cstride + ((size_t)pl.dpos[tile.a] << args.log_n) + off;
+#pragma unroll
+                    for (int j = 0; j < 8; j++) vv2[j] = vrow2[tid + 256 * j];
+                }
+            }
         }
         fwd_rows_pre<A, 2>(v, wd, P.mc);
         fwd_rows_pre<A, 2>(v + 4, wd + 3, P.mc);
@@ -363,6 +372,15 @@ __device__ __forceinline__ void fwd_lo_body(const NttArgs& args, const PolyList&
             const u64 cv = ep.cinv[i], cvs = ep.cinv[ep.num_q + i];
             const u64* add = comp ? fi.add1 : fi.add0;
             u64* orow = fi.out + (((size_t)comp * ep.n_out + i) << args.log_n) + off;
+            if constexpr (std::is_same<A, ArithF64>::value) {
+                if (ep.use_vl == 2) {  // v = ka * x + kb * y, canonical
+                    const double ka = A::from_u64(ep.ka[i]), kb = A::from_u64(ep.kb[i]);
+#pragma unroll
+                    for (int j = 0; j < 8; j++)
+                        vv[j] = A::canonical(A::reduce(A::mulmod_any(A::from_u64(vv[j]), ka, P.mc.q, P.mc.qinv) +
+                                                       A::mulmod_any(A::from_u64(vv2[j]), kb, P.mc.q, P.mc.qinv), P.mc), P.mc);
+                }
+            }
 #pragma unroll
             for (int j = 0; j < 8; j++) {
                 const u32 p = tid + 256 * j;
@@ -607,10 +625,21 @@ __global__ __launch_bounds__(NTT_THREADS) __attribute__((amdgpu_waves_per_eu(3, 
         E* buf0 = (it & 1) ? lds1 : lds0;  // three exchanges per item: the buffers swap roles from item to item
         E* buf1 = (it & 1) ? lds0 : lds1;
         if constexpr (MUL) {
+            if (args.use_lin) {  // uniform
+                const double ka = A::from_u64(args.lin_ka), kb = A::from_u64(args.lin_kb);
 #pragma unroll
-            for (int j = 0; j < 4; j++) {
-                v[2 * j] = A::mulmod_any(A::from_u64(raw[j].x), A::from_u64(raw2[j].x), P.mc.q, P.mc.qinv);
-                v[2 * j + 1] = A::mulmod_any(A::from_u64(raw[j].y), A::from_u64(raw2[j].y), P.mc.q, P.mc.qinv);
+                for (int j = 0; j < 4; j++) {
+                    v[2 * j] = A::reduce(A::mulmod_any(A::from_u64(raw[j].x), ka, P.mc.q, P.mc.qinv) +
+                                         A::mulmod_any(A::from_u64(raw2[j].x), kb, P.mc.q, P.mc.qinv), P.mc);
+                    v[2 * j + 1] = A::reduce(A::mulmod_any(A::from_u64(raw[j].y), ka, P.mc.q, P.mc.qinv) +
+                                             A::mulmod_any(A::from_u64(raw2[j].y), kb, P.mc.q, P.mc.qinv), P.mc);
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; j++) {
+                    v[2 * j] = A::mulmod_any(A::from_u64(raw[j].x), A::from_u64(raw2[j].x), P.mc.q, P.mc.qinv);
+                    v[2 * j + 1] = A::mulmod_any(A::from_u64(raw[j].y), A::from_u64(raw2[j].y), P.mc.q, P.mc.qinv);
+                }
             }
         } else {
 #pragma unroll
@@ -975,9 +1004,11 @@ static void launch_hi_conv(u32 log_hi, u32 ap, dim3 grid, hipStream_t st, const 
 static hipError_t launch_ntt_any(const ckks_ctx* c, bool inverse, const u64* src, size_t src_bstride, u64* dst,
                                  size_t dst_bstride, const PolyList& pl, u32 batch, hipStream_t st, const u64* const* src_ptrs,
                                  const FwdEpilogue* epilogue, const TwF* inv_scale, const ConvPrologue* conv, bool hi_only = false,
-                                 const u64* const* mul_ptrs = nullptr) {
+                                 const u64* const* mul_ptrs = nullptr, const u64* lin_k = nullptr) {
     if (pl.n == 0 || batch == 0) return hipSuccess;
     if (mul_ptrs && (!inverse || !src_ptrs || !ntt_has_modup(c))) return hipErrorInvalidValue;
+    if (lin_k && (!mul_ptrs || pl.n != 1)) return hipErrorInvalidValue;
+    if (epilogue && epilogue->use_vl == 2 && !c->ntt_f64) return hipErrorInvalidValue;
     if (hi_only && (!conv || epilogue)) return hipErrorInvalidValue;
     if (src_ptrs && batch > KS_MAX_BATCH) return hipErrorInvalidValue;
     if (epilogue && (inverse || !ntt_has_epilogue(c) || batch > 2 * KS_MAX_BATCH)) return hipErrorInvalidValue;
@@ -1010,6 +1041,10 @@ static hipError_t launch_ntt_any(const ckks_ctx* c, bool inverse, const u64* src
         args.mul_list.p[b] = (mul_ptrs && b < batch) ? mul_ptrs[b] : nullptr;
     }
     args.inv_scale = inv_scale;
+    args.use_lin = lin_k ? 1 : 0;
+    args.lin_ka = lin_k ? lin_k[0] : 0;
+    args.lin_kb = lin_k ? lin_k[1] : 0;
+    args.pad2 = 0;
     const u32 polys = pl.n * batch;
     const dim3 block(NTT_THREADS);
     const double pass_bytes = 16.0 * polys * c->N;
@@ -1050,7 +1085,7 @@ static hipError_t launch_ntt_any(const ckks_ctx* c, bool inverse, const u64* src
             }
             if (hi_only) return hipGetLastError();  // the caller's own lo pass follows (launch_ntt_lo_mac)
             if (epilogue) {  // reads w and v, writes the quotients (plus the addends it reads)
-                ProfScope ps__(c, K_NTT_FWD_LO, st, 1.5 * pass_bytes, lo_ops);
+                ProfScope ps__(c, K_NTT_FWD_LO, st, (epilogue->use_vl == 2 ? 2.0 : 1.5) * pass_bytes, lo_ops);
                 if (f64) launch_lo_div<ArithF64>(lo_items, grid_lo, st, second, pd, *epilogue);
                 else launch_lo_div<ArithU64>(lo_items, grid_lo, st, second, pd, *epilogue);
             } else {
@@ -1075,9 +1110,9 @@ static hipError_t launch_ntt_any(const ckks_ctx* c, bool inverse, const u64* src
 
 hipError_t launch_ntt(const ckks_ctx* c, bool inverse, const u64* src, size_t src_bstride, u64* dst, size_t dst_bstride,
                       const PolyList& pl, u32 batch, hipStream_t st, const u64* const* src_ptrs, const FwdEpilogue* epilogue,
-                      const TwF* inv_scale, const u64* const* mul_ptrs) {
+                      const TwF* inv_scale, const u64* const* mul_ptrs, const u64* lin_k) {
     return launch_ntt_any(c, inverse, src, src_bstride, dst, dst_bstride, pl, batch, st, src_ptrs, epilogue, inv_scale, nullptr, false,
-                          mul_ptrs);
+                          mul_ptrs, lin_k);
 }
 
 hipError_t launch_ntt_modup(const ckks_ctx* c, u32 level, u32 j, const double* y, size_t y_bstride, u64* dst, size_t dst_bstride,
