@@ -327,6 +327,7 @@ def main():
     # ---- the two microbenchmark shapes, reported next to the headline value ------------------------
     hx.ckks_ctx_set_overlap(ctx, not args.single_stream)
     rotation_microbench(hx, torch, ctx, ins[0], keys, level, N, ws, result)
+    base_keys = [k for k in keys if k is not None]
     # accumulator merge (the optimised pipeline's block-group transition): 4 intermediate ciphertexts with 8192
     # occupied slots each -> one full ciphertext, at the level the block slice leaves its outputs on
     acc_level, acc_g, acc_sts = level - 5, 4, 8192
