@@ -71,6 +71,8 @@ def parse_args():
     ap.add_argument("--no-microbench", action="store_true", help="skip the rotation and NTT microbenchmarks")
     ap.add_argument("--rotations-only", action="store_true",
                     help="only the rotation microbenchmark (64 hoisted + 64 unhoisted rotations, three times each): for profiling runs")
+    ap.add_argument("--ntt-only", action="store_true",
+                    help="only the NTT microbenchmark (64 x 30 limb transforms at N = 2^16, forward and inverse, six times): for profiling runs")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run the library's plain copy kernel on one ciphertext (24 MiB in, 24 MiB out): the known-size "
                          "dispatch that hardware-counter runs are scaled by")
@@ -159,6 +161,27 @@ def rotation_microbench(hx, torch, ctx, ct, keys, level, N, ws, result):
         result["rotation_%s_effective_GBs" % name] = rate * mib * 2**20 / 1e9
 
 
+def ntt_microbench(hx, torch, result):
+    from workloads import CONFIGS, uniform_residues
+    # NTT microbenchmark: 64 polynomials x 30 limbs at N = 2^16, forward then inverse
+    p2 = CONFIGS["cfg2_ntt"].params()
+    ctx2 = hx.Context(p2)
+    polys = hx.from_host(uniform_residues((64, p2.num_q, p2.n), p2.moduli, "cfg2"))
+    idx2 = list(range(p2.num_q))
+    hx.ckks_ntt_fwd(ctx2, polys, idx2)
+    hx.ckks_ntt_inv(ctx2, polys, idx2)
+    torch.cuda.synchronize()
+    reps = 5
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        hx.ckks_ntt_fwd(ctx2, polys, idx2)
+        hx.ckks_ntt_inv(ctx2, polys, idx2)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    result["ntt_limbs_per_s"] = 2 * 64 * p2.num_q * reps / dt          # forward and inverse limb transforms
+    result["ntt_butterflies_per_s"] = result["ntt_limbs_per_s"] * (p2.n // 2) * p2.log_n
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -171,6 +194,11 @@ def main():
     import paper_2604_16834_amd as hx
     from workloads import CONFIGS, conv_tap_offsets, uniform_residues
 
+    if args.ntt_only:
+        result = {"workload": "cfg2_ntt (the NTT microbenchmark of the default run)"}
+        ntt_microbench(hx, torch, result)
+        print(json.dumps(result))
+        return
     wl = CONFIGS[args.workload]
     params = wl.params()
     ctx = hx.Context(params)
@@ -452,23 +480,7 @@ def main():
                              "ms_two_steps_while_staging": both_dt * 1e3, "ms_two_steps": 2 * ms_per_step,
                              "staging_ms_hidden": alone * 1e3 + 2 * ms_per_step - both_dt * 1e3}
     del host_b, staged
-    # NTT microbenchmark: 64 polynomials x 30 limbs at N = 2^16, forward then inverse
-    p2 = CONFIGS["cfg2_ntt"].params()
-    ctx2 = hx.Context(p2)
-    polys = hx.from_host(uniform_residues((64, p2.num_q, N), p2.moduli, "cfg2"))
-    idx2 = list(range(p2.num_q))
-    hx.ckks_ntt_fwd(ctx2, polys, idx2)
-    hx.ckks_ntt_inv(ctx2, polys, idx2)
-    torch.cuda.synchronize()
-    reps = 5
-    t0 = time.perf_counter()
-    for _ in range(reps):
-        hx.ckks_ntt_fwd(ctx2, polys, idx2)
-        hx.ckks_ntt_inv(ctx2, polys, idx2)
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    result["ntt_limbs_per_s"] = 2 * 64 * p2.num_q * reps / dt          # forward and inverse limb transforms
-    result["ntt_butterflies_per_s"] = result["ntt_limbs_per_s"] * (N // 2) * p2.log_n
+    ntt_microbench(hx, torch, result)
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, params, args.alignment, act_merged)
