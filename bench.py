@@ -28,7 +28,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 # vector ALU peak: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3e12 lane-operations/s (32-bit integer or fp64 FMA alike)
 ALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
-# Kernels whose limiter is arithmetic, should one of them become the dominant kernel (derivations in the design doc):
+# Kernels whose limiter is arithmetic, should one of them become the dominant kernel:
 # a double-precision butterfly of the NTT = 10 fp64 operations (6 for the twiddle product, 2 for sum and
 # difference, 2 for the amortised re-centring); the multiply-accumulate on the matrix cores = 49 digit
 # products x 2 operations per modular multiply-add against the dense 8-bit integer peak.
