@@ -706,8 +706,10 @@ int run_relayout(const ckks_ctx* c, u32 level, u32 n_ct, const u64* const* cts, 
 size_t ws_relayout_deferred(const ckks_ctx* c, u32 level, u32 n_ct, u32 n_lo, u32 n_hi) {
     const size_t N = c->N, xel = 2 * (size_t)c->ext_limbs(level) * N, xel1 = 2 * (size_t)c->ext_limbs(level - 1) * N, ctl1 = 2 * (size_t)level * N;
     const size_t nb = n_ct < CT_BATCH ? n_ct : CT_BATCH;
+    // the first rotations go through the fused eight-rotation inner product: its prepared keys, one set per group of eight
+    const size_t taps = c->live_digits(level) <= 4 ? (size_t)((n_lo + 7) / 8) * blk(key_inner_taps_scratch_elems(c, level, 8)) : 0;
     return blk(nb * n_lo * xel) + blk(nb * n_hi * xel) + blk(nb * n_hi * ctl1) + blk(nb * n_hi * xel1) + blk(nb * xel1) +
-           ws_ks(c, level, CT_BATCH, CT_BATCH);
+           ws_ks(c, level, CT_BATCH, CT_BATCH) + taps;
 }
 
 int run_relayout_deferred(const ckks_ctx* c, u32 level, u32 n_ct, const u64* const* cts, u32 n_lo, const ckks_key* const* lo_keys,
@@ -723,6 +725,15 @@ int run_relayout_deferred(const ckks_ctx* c, u32 level, u32 n_ct, const u64* con
     KsWs ws;
     const size_t ks_bytes = ws_ks(c, level, CT_BATCH, CT_BATCH);
     u64* ks_region = ar.take(ks_bytes / sizeof(u64));
+    // Up to eight first rotations of a batch of ciphertexts in one launch (the digits are read once for the eight, not once
+    // per rotation): the keyed offsets in groups of eight, each group with its prepared keys (made by the first batch).
+    const bool fused_lo = c->live_digits(level) <= 4;
+    std::vector<u32> keyed;
+    for (u32 l = 0; l < n_lo; l++)
+        if (g_lo[l] != 1) keyed.push_back(l);
+    const u32 n_groups = fused_lo ? (u32)((keyed.size() + 7) / 8) : 0;
+    const size_t ksc = key_inner_taps_scratch_elems(c, level, 8);
+    u64* kscratch = n_groups ? ar.take((size_t)n_groups * ksc) : nullptr;
     if (!ar.ok()) return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for the re-layout");
     auto ks_at = [&](u32 lv) {
         Arena sub(ks_region, ks_bytes);
@@ -743,9 +754,22 @@ int run_relayout_deferred(const ckks_ctx* c, u32 level, u32 n_ct, const u64* con
             for (u32 b = 0; b < n; b++) xo[b] = X + ((size_t)b * n_lo + l) * xel;
             if (g_lo[l] == 1) {
                 for (u32 b = 0; b < n; b++) HIP_TRY(launch_scale_p_ext(c, level, in[b], xo[b], st));
-            } else {
+            } else if (!fused_lo) {
                 HIP_TRY(launch_key_inner_ext(c, level, dsrc(c, ws, 0), lo_keys[l]->d_key, g_lo[l], in, nullptr, nullptr, xo, n, st));
             }
+        }
+        for (u32 g = 0; g < n_groups; g++) {  // X[b][l] = term b * n_lo + l of a [2][E][N] array per term
+            const u64 *tkeys[8], *tmasks[8];
+            u32 tg[8], ttap[8], nt = 0;
+            for (size_t i = (size_t)g * 8; i < keyed.size() && nt < 8; i++) {
+                const u32 l = keyed[i];
+                tkeys[nt] = lo_keys[l]->d_key;
+                tmasks[nt] = nullptr;
+                tg[nt] = g_lo[l];
+                ttap[nt++] = l;
+            }
+            HIP_TRY(launch_key_inner_taps(c, level, dsrc(c, ws, 0), tkeys, tg, tmasks, ttap, nt, in, X, XLayout::classic(c->ext_limbs(level), N), 0,
+                                          n_lo, n, kscratch + (size_t)g * ksc, c0 == 0, st));
         }
         HIP_TRY(launch_relayout_mac(c, level, true, X, masks, Vacc, n, n_lo, n_hi, st));
         const u32 n_v = n * n_hi;

@@ -403,7 +403,7 @@ __global__ __launch_bounds__(KS_THREADS) void mask_keys_kernel(TapSet T, u64* __
         if (e <= level) mp[((size_t)i * (level + 1) + e) * N + x] = mulmod_barrett(T.centre_mask[(size_t)e * N + x], m.q - negp[e], m);
         return;
     }
-    const u64 mv = T.mask[i][(size_t)e * N + x];
+    const u64 mv = T.mask[i] ? T.mask[i][(size_t)e * N + x] : 1;  // no mask: the key as it is, and P
     for (u32 j = 0; j < beta; j++)
         for (u32 comp = 0; comp < 2; comp++)
             mk[((((size_t)i * beta + j) * 2 + comp) * E + e) * N + x] = mulmod_barrett(mv, T.key[i][(((size_t)j * 2 + comp) * M + t) * N + x], m);
