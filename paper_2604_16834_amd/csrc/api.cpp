@@ -706,10 +706,8 @@ int run_relayout(const ckks_ctx* c, u32 level, u32 n_ct, const u64* const* cts, 
 size_t ws_relayout_deferred(const ckks_ctx* c, u32 level, u32 n_ct, u32 n_lo, u32 n_hi) {
     const size_t N = c->N, xel = 2 * (size_t)c->ext_limbs(level) * N, xel1 = 2 * (size_t)c->ext_limbs(level - 1) * N, ctl1 = 2 * (size_t)level * N;
     const size_t nb = n_ct < CT_BATCH ? n_ct : CT_BATCH;
-    // the first rotations go through the fused eight-rotation inner product: its prepared keys, one set per group of eight
-    const size_t taps = c->live_digits(level) <= 4 ? (size_t)((n_lo + 7) / 8) * blk(key_inner_taps_scratch_elems(c, level, 8)) : 0;
     return blk(nb * n_lo * xel) + blk(nb * n_hi * xel) + blk(nb * n_hi * ctl1) + blk(nb * n_hi * xel1) + blk(nb * xel1) +
-           ws_ks(c, level, CT_BATCH, CT_BATCH) + taps;
+           ws_ks(c, level, CT_BATCH, CT_BATCH);
 }
 
 int run_relayout_deferred(const ckks_ctx* c, u32 level, u32 n_ct, const u64* const* cts, u32 n_lo, const ckks_key* const* lo_keys,
@@ -726,14 +724,12 @@ int run_relayout_deferred(const ckks_ctx* c, u32 level, u32 n_ct, const u64* con
     const size_t ks_bytes = ws_ks(c, level, CT_BATCH, CT_BATCH);
     u64* ks_region = ar.take(ks_bytes / sizeof(u64));
     // Up to eight first rotations of a batch of ciphertexts in one launch (the digits are read once for the eight, not once
-    // per rotation): the keyed offsets in groups of eight, each group with its prepared keys (made by the first batch).
+    // per rotation): the keyed offsets in groups of eight.
     const bool fused_lo = c->live_digits(level) <= 4;
     std::vector<u32> keyed;
     for (u32 l = 0; l < n_lo; l++)
         if (g_lo[l] != 1) keyed.push_back(l);
     const u32 n_groups = fused_lo ? (u32)((keyed.size() + 7) / 8) : 0;
-    const size_t ksc = key_inner_taps_scratch_elems(c, level, 8);
-    u64* kscratch = n_groups ? ar.take((size_t)n_groups * ksc) : nullptr;
     if (!ar.ok()) return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for the re-layout");
     auto ks_at = [&](u32 lv) {
         Arena sub(ks_region, ks_bytes);
@@ -759,17 +755,16 @@ int run_relayout_deferred(const ckks_ctx* c, u32 level, u32 n_ct, const u64* con
             }
         }
         for (u32 g = 0; g < n_groups; g++) {  // X[b][l] = term b * n_lo + l of a [2][E][N] array per term
-            const u64 *tkeys[8], *tmasks[8];
+            const u64* tkeys[8];
             u32 tg[8], ttap[8], nt = 0;
             for (size_t i = (size_t)g * 8; i < keyed.size() && nt < 8; i++) {
                 const u32 l = keyed[i];
                 tkeys[nt] = lo_keys[l]->d_key;
-                tmasks[nt] = nullptr;
                 tg[nt] = g_lo[l];
                 ttap[nt++] = l;
             }
-            HIP_TRY(launch_key_inner_taps(c, level, dsrc(c, ws, 0), tkeys, tg, tmasks, ttap, nt, in, X, XLayout::classic(c->ext_limbs(level), N), 0,
-                                          n_lo, n, kscratch + (size_t)g * ksc, c0 == 0, st));
+            HIP_TRY(launch_key_inner_taps(c, level, dsrc(c, ws, 0), tkeys, tg, nullptr, ttap, nt, in, X, XLayout::classic(c->ext_limbs(level), N), 0,
+                                          n_lo, n, nullptr, false, st, nullptr, 0, true));
         }
         HIP_TRY(launch_relayout_mac(c, level, true, X, masks, Vacc, n, n_lo, n_hi, st));
         const u32 n_v = n * n_hi;
@@ -1093,6 +1088,27 @@ int ckks_rotate_hoisted(const ckks_ctx* c, const uint64_t* d_ct, uint32_t level,
         nb = 0;
         return rc;
     };
+    const bool fused_hoist = hoisted && c->live_digits(level) <= 4;
+    auto flush_hoisted = [&]() -> int {
+        const KsWs& lw = lane_ws[lane];
+        hipStream_t ls = lane ? c->side : st;
+        const u64* tkeys[8];
+        u32 tg[8], ttap[8];
+        for (u32 b = 0; b < nb; b++) {
+            tkeys[b] = pend_key[b]->d_key;
+            tg[b] = items[b].g;
+            ttap[b] = b;
+            items[b].g = 1;  // the division's last step adds nothing: c0 is inside the sum already
+        }
+        if (hipError_t e = launch_key_inner_taps(c, level, dsrc(c, lw, 0), tkeys, tg, nullptr, ttap, nb, &ct, lw.v,
+                                                 XLayout::classic(c->ext_limbs(level), N), 0, 0, 1, nullptr, false, ls, nullptr, 0, true);
+            e != hipSuccess)
+            return set_hip_err(c, e);
+        int rc = run_moddown(c, level, lw, nb, items, ls);
+        nb = 0;
+        if (two_lanes) lane ^= 1;
+        return rc;
+    };
     for (u32 t = 0; t < n_rot; t++) {
         const u32 g = ckks_galois_element(c, h_offsets[t]);
         u64* out = (u64*)h_d_outs[t];
@@ -1100,8 +1116,16 @@ int ckks_rotate_hoisted(const ckks_ctx* c, const uint64_t* d_ct, uint32_t level,
             if (hipError_t e = launch_copy(ct, out, 2 * L1 * N, st); e != hipSuccess) return join(set_hip_err(c, e));
             continue;
         }
-        if (hoisted) {
-            // same digits, one key per rotation; the digits are read through sigma_g
+        if (hoisted && fused_hoist) {
+            // same digits, one key per rotation: the rotations of a batch share one launch that reads the digits once and
+            // leaves P sigma_g(c0) + inner product on the extended basis (its ModDown is the rotation, c0 included)
+            pend_key[nb] = keys[t];
+            items[nb] = FinalItem{nullptr, nullptr, nullptr, out, g, 0};
+            if (++nb == rb) {
+                if (int rc = flush_hoisted()) return join(rc);
+            }
+        } else if (hoisted) {
+            // many digits: one launch per rotation; the digits are read through sigma_g
             const KsWs& lw = lane_ws[lane];
             hipStream_t ls = lane ? c->side : st;
             if (hipError_t e = launch_key_inner(c, level, dsrc(c, lw, 0), keys[t]->d_key, g, lw.v + nb * lw.v_b, ls); e != hipSuccess)
@@ -1122,6 +1146,8 @@ int ckks_rotate_hoisted(const ckks_ctx* c, const uint64_t* d_ct, uint32_t level,
     }
     if (nb && !hoisted) {
         if (int rc = flush_unhoisted()) return rc;
+    } else if (nb && fused_hoist) {
+        if (int rc = flush_hoisted()) return join(rc);
     } else if (nb) {
         int rc = run_moddown(c, level, lane_ws[lane], nb, items, lane ? c->side : st);
         if (rc) return join(rc);

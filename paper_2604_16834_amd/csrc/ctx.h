@@ -271,7 +271,7 @@ hipError_t launch_key_inner_ext(const ckks_ctx* c, u32 level, const DigitSrc& di
 hipError_t launch_key_inner_taps(const ckks_ctx* c, u32 level, const DigitSrc& digits, const u64* const* keys,
                                  const u32* gs, const u64* const* masks, const u32* taps, u32 n_taps, const u64* const* c0s,
                                  u64* xs, XLayout xl, u32 k0, u32 k_bstride, u32 n, u64* scratch, bool prepare, hipStream_t st,
-                                 const u64* centre_mask = nullptr, u32 centre_tap = 0);
+                                 const u64* centre_mask = nullptr, u32 centre_tap = 0, bool direct_keys = false);
 size_t key_inner_taps_scratch_elems(const ckks_ctx* c, u32 level, u32 n_taps);
 // merged: the dropped limbs are q_level and the special primes (division by P*q_level, results on limbs 0..level-1)
 hipError_t launch_moddown_conv(const ckks_ctx* c, u32 level, bool merged, const u64* v, u64* w, u32 batch, hipStream_t st);

@@ -416,13 +416,17 @@ __global__ __launch_bounds__(KS_THREADS) void key_inner_taps_kernel(DigitSrc dig
                                                                     const u64* __restrict__ mk, const u64* __restrict__ mp,
                                                                     PtrList8 c0s, u64* __restrict__ xs, XLayout xl, u32 k0base,
                                                                     u32 k_bstride, const ModConst* __restrict__ mc, u32 log_n,
-                                                                    u32 level, u32 num_q, u32 E, u32 n) {
+                                                                    u32 level, u32 num_q, u32 E, u32 n, u32 M, const u64* __restrict__ negp) {
+    // negp != nullptr: no masks; the keys are read where they are (T.key[i]: [dnum][2][M][N]) and mask * P is P itself
     const u32 N = 1u << log_n;
     const u32 xsrc = blockIdx.x * KS_THREADS + threadIdx.x;
     if (xsrc >= N) return;
     const u32 e = blockIdx.y;
-    const ModConst m = mc[e <= level ? e : num_q + (e - level - 1)];
+    const u32 t = e <= level ? e : num_q + (e - level - 1);
+    const ModConst m = mc[t];
     const bool has_add = e <= level;
+    const bool direct = negp != nullptr;
+    const u64 pres = (direct && has_add) ? m.q - negp[e] : 0;  // P mod q_e
     u64 dv[CT_BATCH][BETA], cv[CT_BATCH];
 #pragma unroll
     for (u32 b = 0; b < CT_BATCH; b++) {
@@ -436,10 +440,11 @@ __global__ __launch_bounds__(KS_THREADS) void key_inner_taps_kernel(DigitSrc dig
         u64 k0[BETA], k1[BETA];
 #pragma unroll
         for (u32 j = 0; j < BETA; j++) {
-            k0[j] = mk[((((size_t)i * BETA + j) * 2 + 0) * E + e) * N + x];
-            k1[j] = mk[((((size_t)i * BETA + j) * 2 + 1) * E + e) * N + x];
+            const u64* kb = direct ? T.key[i] + (((size_t)j * 2) * M + t) * N + x : mk + ((((size_t)i * BETA + j) * 2) * E + e) * N + x;
+            k0[j] = kb[0];
+            k1[j] = kb[(size_t)(direct ? M : E) * N];
         }
-        const u64 kp = has_add ? mp[((size_t)i * (level + 1) + e) * N + x] : 0;
+        const u64 kp = direct ? pres : (has_add ? mp[((size_t)i * (level + 1) + e) * N + x] : 0);
         u64* ot = xs + xl.at(k0base + T.tap[i], 0, e, x);
         if (SMALL) {
             Split50 s0[BETA], s1[BETA];
@@ -507,16 +512,23 @@ size_t key_inner_taps_scratch_elems(const ckks_ctx* c, u32 level, u32 n_taps) {
 hipError_t launch_key_inner_taps(const ckks_ctx* c, u32 level, const DigitSrc& digits, const u64* const* keys,
                                  const u32* gs, const u64* const* masks, const u32* taps, u32 n_taps, const u64* const* c0s,
                                  u64* xs, XLayout xl, u32 k0, u32 k_bstride, u32 n, u64* scratch, bool prepare, hipStream_t st,
-                                 const u64* centre_mask, u32 centre_tap) {
+                                 const u64* centre_mask, u32 centre_tap, bool direct_keys) {
     if (n_taps == 0 || n == 0) return hipSuccess;
     if (n_taps > 8 || n > CT_BATCH) return hipErrorInvalidValue;
+    if (direct_keys) {  // no masks, no prepared copies: the keys are read where they are
+        if (centre_mask) return hipErrorInvalidValue;
+        for (u32 i = 0; i < n_taps; i++)
+            if (masks && masks[i]) return hipErrorInvalidValue;
+    } else if (!scratch || !masks) {
+        return hipErrorInvalidValue;
+    }
     const u32 E = c->ext_limbs(level), beta = c->live_digits(level);
     if (beta > 4) return hipErrorNotSupported;
     TapSet T;
     const u64 two_n = 2ull * c->N;
     for (u32 i = 0; i < 8; i++) {
         T.key[i] = i < n_taps ? keys[i] : nullptr;
-        T.mask[i] = i < n_taps ? masks[i] : nullptr;
+        T.mask[i] = (i < n_taps && masks) ? masks[i] : nullptr;
         T.tap[i] = i < n_taps ? taps[i] : 0;
         u64 inv = 1;
         if (i < n_taps) {  // g^-1 mod 2N: g is odd, the group has exponent N/2
@@ -534,10 +546,11 @@ hipError_t launch_key_inner_taps(const ckks_ctx* c, u32 level, const DigitSrc& d
     PtrList8 cl;
     for (u32 b = 0; b < KS_MAX_BATCH; b++) cl.p[b] = b < n ? c0s[b] : nullptr;
     u64* mk = scratch;
-    u64* mp = scratch + (size_t)n_taps * beta * 2 * E * c->N;
+    u64* mp = direct_keys ? nullptr : scratch + (size_t)n_taps * beta * 2 * E * c->N;
     const u32 nxb = (c->N + KS_THREADS - 1) / KS_THREADS;
-    if (prepare) {
-        const u64* negp = c->d_moddown + 2 * c->k_pad + (size_t)c->k_pad * c->num_q + 2 * c->num_q;
+    const u64* negp = c->d_moddown + 2 * c->k_pad + (size_t)c->k_pad * c->num_q + 2 * c->num_q;
+    const u64* negp_direct = direct_keys ? negp : nullptr;
+    if (prepare && !direct_keys) {
         ProfScope ps__(c, K_MASK_MUL, st, 8.0 * c->N * n_taps * (E * (4.0 * beta + 1.0) + level + 1.0), 2.0 * c->N * n_taps * E * beta);
         hipLaunchKernelGGL(mask_keys_kernel, dim3(nxb, E, n_taps + (centre_mask ? 1 : 0)), dim3(KS_THREADS), 0, st, T, mk, mp, negp, c->d_mc, c->N, level, c->num_q,
                            c->M, E, beta);
@@ -550,10 +563,10 @@ hipError_t launch_key_inner_taps(const ckks_ctx* c, u32 level, const DigitSrc& d
     do {                                                                                                                             \
         if (c->small_q)                                                                                                              \
             hipLaunchKernelGGL((key_inner_taps_kernel<B_, true>), grid, dim3(KS_THREADS), 0, st, digits, T, mk, mp, cl, xs, xl, \
-                               k0, k_bstride, c->d_mc, c->log_n, level, c->num_q, E, n);                                             \
+                               k0, k_bstride, c->d_mc, c->log_n, level, c->num_q, E, n, c->M, negp_direct);                          \
         else                                                                                                                         \
             hipLaunchKernelGGL((key_inner_taps_kernel<B_, false>), grid, dim3(KS_THREADS), 0, st, digits, T, mk, mp, cl, xs, xl, \
-                               k0, k_bstride, c->d_mc, c->log_n, level, c->num_q, E, n);                                             \
+                               k0, k_bstride, c->d_mc, c->log_n, level, c->num_q, E, n, c->M, negp_direct);                          \
     } while (0)
     if (beta == 1) KI_TAPS(1);
     else if (beta == 2) KI_TAPS(2);
