@@ -142,4 +142,6 @@ CONFIGS: Dict[str, Workload] = {
     "small_rotations": Workload("small_rotations", 13, 7, 3, 3, n_rot=6),
     "small_conv": Workload("small_conv", 13, 5, 2, 3, 8, 8, 64, 3, 2),
     "small_block": Workload("small_block", 12, 8, 3, 3, 8, 8, 32, 2, 2),
+    # six one-limb digits: more than the fused multi-rotation launches take (the one-launch-per-tap paths)
+    "small_conv_d6": Workload("small_conv_d6", 12, 6, 2, 6, 8, 8, 32, 3, 2),
 }
