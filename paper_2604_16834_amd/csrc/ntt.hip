@@ -760,16 +760,17 @@ struct ConvPrologue {
 
 // the source residues of one point: no branch around the loads (entries beyond the nd source limbs re-read the last
 // one against a zero constant)
-template <int AP>
+// ND <= AP: the entries that are read and multiplied (a row of the constants has AP, the last AP - ND of them zero)
+template <int AP, int ND>
 __device__ __forceinline__ void conv_load(double (&yv)[AP], const double* __restrict__ yp, size_t N, u32 nd) {
 #pragma unroll
-    for (int a = 0; a < AP; a++) yv[a] = yp[(size_t)((u32)a < nd ? a : nd - 1) * N];
+    for (int a = 0; a < ND; a++) yv[a] = yp[(size_t)((u32)a < nd ? a : nd - 1) * N];
 }
-template <int AP>
+template <int AP, int ND>
 __device__ __forceinline__ double conv_sum(const double (&yv)[AP], const TwF* cw, double q, double qinv) {
     double s = 0.0;
 #pragma unroll
-    for (int a = 0; a < AP; a++) {
+    for (int a = 0; a < ND; a++) {
         s += ArithF64::mulmod(yv[a], cw[a].w, cw[a].wq, q);
         if (a == 7 && AP > 8) s = __builtin_fma(-ArithF64::round_mul(s, qinv), q, s);  // keeps longer sums below 2^53
     }
@@ -778,7 +779,7 @@ __device__ __forceinline__ double conv_sum(const double (&yv)[AP], const TwF* cw
 
 // One workgroup converts and transforms the same tile of T target limbs: the source residues are fetched once for all T
 // (the fetch, from L2 after the first, is what bounds a one-target-per-workgroup version).
-template <int LOG_HI, int AP, int T>
+template <int LOG_HI, int AP, int T, int ND = AP>
 __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_hi_conv_kernel(NttArgs args, PolyList pl, ConvPrologue cp) {
     typedef ArithF64 A;
     typedef double E;
@@ -805,9 +806,9 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_hi_conv_kernel(NttArgs ar
 #pragma unroll
             for (int kc = 0; kc < KC; kc++) {
                 double yv[AP];
-                conv_load<AP>(yv, y + ((size_t)rr << 11) + kc * 256 + tid, N, cp.nd);
+                conv_load<AP, ND>(yv, y + ((size_t)rr << 11) + kc * 256 + tid, N, cp.nd);
 #pragma unroll
-                for (int t = 0; t < T; t++) v[t][rr * KC + kc] = conv_sum<AP>(yv, cw[t], P[t].mc.q, P[t].mc.qinv);
+                for (int t = 0; t < T; t++) v[t][rr * KC + kc] = conv_sum<AP, ND>(yv, cw[t], P[t].mc.q, P[t].mc.qinv);
             }
 #pragma unroll
         for (int t = 0; t < T; t++) {
@@ -827,9 +828,9 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_hi_conv_kernel(NttArgs ar
 #pragma unroll
         for (int j = 0; j < 8; j++) {
             double yv[AP];
-            conv_load<AP>(yv, y + ((size_t)(r0 + R8 * j) << 11) + col, N, cp.nd);
+            conv_load<AP, ND>(yv, y + ((size_t)(r0 + R8 * j) << 11) + col, N, cp.nd);
 #pragma unroll
-            for (int t = 0; t < T; t++) v[t][j] = conv_sum<AP>(yv, cw[t], P[t].mc.q, P[t].mc.qinv);
+            for (int t = 0; t < T; t++) v[t][j] = conv_sum<AP, ND>(yv, cw[t], P[t].mc.q, P[t].mc.qinv);
         }
         const u32 G = tid >> 5, cg = tid & 31;
 #pragma unroll
@@ -985,8 +986,12 @@ constexpr u32 CONV_TARGETS = 4;  // target limbs per workgroup of the converting
 template <int LOG_HI>
 static void launch_hi_conv_ap(u32 ap, dim3 grid, hipStream_t st, const NttArgs& args, const PolyList& pl, const ConvPrologue& cp) {
     constexpr int T = CONV_TARGETS;
-    if (ap == 4) hipLaunchKernelGGL((ntt_fwd_hi_conv_kernel<LOG_HI, 4, T>), grid, dim3(NTT_THREADS), 0, st, args, pl, cp);
+    if (ap == 4 && cp.nd == 1)  // the rescale: one dropped limb
+        hipLaunchKernelGGL((ntt_fwd_hi_conv_kernel<LOG_HI, 4, T, 1>), grid, dim3(NTT_THREADS), 0, st, args, pl, cp);
+    else if (ap == 4) hipLaunchKernelGGL((ntt_fwd_hi_conv_kernel<LOG_HI, 4, T>), grid, dim3(NTT_THREADS), 0, st, args, pl, cp);
     else if (ap == 8) hipLaunchKernelGGL((ntt_fwd_hi_conv_kernel<LOG_HI, 8, T>), grid, dim3(NTT_THREADS), 0, st, args, pl, cp);
+    else if (ap == 12 && cp.nd == 9)  // eight special primes and the dropped limb: three of the twelve entries are padding
+        hipLaunchKernelGGL((ntt_fwd_hi_conv_kernel<LOG_HI, 12, T, 9>), grid, dim3(NTT_THREADS), 0, st, args, pl, cp);
     else if (ap == 12) hipLaunchKernelGGL((ntt_fwd_hi_conv_kernel<LOG_HI, 12, T>), grid, dim3(NTT_THREADS), 0, st, args, pl, cp);
     else hipLaunchKernelGGL((ntt_fwd_hi_conv_kernel<LOG_HI, 16, T>), grid, dim3(NTT_THREADS), 0, st, args, pl, cp);
 }
