@@ -518,6 +518,51 @@ def test_two_stream_activation_replays_from_a_graph():
             assert all(torch.equal(a, b) for a, b in zip(outs, ref))
 
 
+def test_deferred_convolution_replays_from_a_graph():
+    """The convolution (deferred, merged division: fused taps, matrix-core sum, conversions and division inside the
+    transforms) captured into a HIP graph: every replay gives the eager, oracle-checked result."""
+    import torch
+    wl = CONFIGS["small_conv"]
+    p = wl.params()
+    orc, ctx = both(p)
+    level = p.num_q - 1
+    s, s_ntt = orc.gen_secret(921)
+    img = image_batch(wl.batch, wl.c_in, wl.height, wl.width)
+    w = conv_weights(wl.c_out, wl.c_in, dist="he_normal")
+    cts = [orc.encrypt(orc.pack_channel(img, c), 2.0 ** 40, level, s_ntt, 922 + c) for c in range(wl.c_in)]
+    offs = conv_tap_offsets(wl.width)
+    keys = {off: orc.gen_rotation_key(s, s_ntt, off, 930 + i) for i, off in enumerate(offs) if off}
+    masks, w_int = orc.conv_operands_ext(w, wl.height, wl.width, wl.batch, level, 2.0 ** 28, p.moduli[level] / 2.0 ** 28)
+    w_moduli = [p.moduli[t] for t in orc.ext_moduli_idx(level)]
+    dkeys = [hx.ckks_key_load(ctx, hx.from_host(keys[off]), hx.ckks_galois_element(ctx, off)) if off in keys else None for off in offs]
+    d_in = [hx.from_host(c) for c in cts]
+    d_masks, d_w = hx.from_host(masks), hx.from_host(w_residues(w_int, w_moduli, len(w_moduli) - 1))
+    outs = [hx.empty(2, level, orc.N) for _ in range(wl.c_out)]
+    mode = hx.HE_CONV_DEFERRED_MERGED
+    ws = hx.empty(hx.he_conv_workspace_bytes(ctx, wl.c_in, wl.c_out, wl.height, wl.width, wl.batch, level, mode) // 8 + 1)
+    st = torch.cuda.Stream()
+    run = lambda: hx.he_conv_batched(ctx, wl.height, wl.width, wl.batch, level, d_in, dkeys, d_masks, d_w, wl.c_out, outs=outs, ws=ws,
+                                     alignment=mode, stream=st.cuda_stream)
+    with torch.cuda.stream(st):
+        run()
+        st.synchronize()
+        ref = [o.clone() for o in outs]
+        want = orc.he_conv_deferred(cts, level, wl.width, keys, masks, w_int, merged=True)
+        for o in range(wl.c_out):
+            assert np.array_equal(hx.to_host(ref[o]), want[o])
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=st):
+            run()
+        for _ in range(3):
+            for o in outs:
+                o.zero_()
+            ws.zero_()
+            torch.randn(1 << 16, device="cuda").sum().item()      # eager work and a synchronisation between replays
+            graph.replay()
+            torch.cuda.synchronize()
+            assert all(torch.equal(a, b) for a, b in zip(outs, ref))
+
+
 # --------------------------------------------------------------------------------- staged keys
 @pytest.mark.parametrize("log_n,num_q,num_p,dnum,bits", [(12, 4, 2, 2, 50), (10, 3, 1, 3, 57), (5, 3, 1, 2, 12)])
 def test_key_expansion_matches_oracle(log_n, num_q, num_p, dnum, bits):
