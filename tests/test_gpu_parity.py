@@ -732,10 +732,10 @@ def test_poly_activation_matches_oracle(n_ct):
         assert np.abs(dec - activation_reference(xs[i])).max() < 1e-3
 
 
-@pytest.mark.parametrize("n_ct,bits", [(1, 50), (10, 50), (2, 56)])
-def test_poly_activation_merged_division_matches_oracle(n_ct, bits):
+@pytest.mark.parametrize("n_ct,bits,log_n", [(1, 50, None), (10, 50, None), (2, 56, None), (2, 50, 14), (1, 50, 15)])
+def test_poly_activation_merged_division_matches_oracle(n_ct, bits, log_n):
     wl = CONFIGS["small_block"]
-    p = make_params(wl.log_n, wl.num_q, wl.num_p, wl.dnum, bits=bits)
+    p = make_params(log_n or wl.log_n, wl.num_q, wl.num_p, wl.dnum, bits=bits)
     orc, ctx = both(p)
     level = p.num_q - 1
     s, s_ntt = orc.gen_secret(351)
