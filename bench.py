@@ -161,6 +161,43 @@ def rotation_microbench(hx, torch, ctx, ct, keys, level, N, ws, result):
         result["rotation_%s_effective_GBs" % name] = rate * mib * 2**20 / 1e9
 
 
+def conv_microbench(hx, torch, name, result):
+    """The convolution alone at another benchmark shape (deferred ModDown merged with the rescale, bounded weights)."""
+    import numpy as np
+    from workloads import CONFIGS, conv_tap_offsets, conv_weights, uniform_residues
+    wl = CONFIGS[name]
+    params = wl.params()
+    ctx = hx.Context(params)
+    N, level, q = params.n, params.num_q - 1, params.moduli
+    M = params.num_q + params.num_p
+    ins = [hx.from_host(uniform_residues((2, level + 1, N), q[:level + 1], name + "in%d" % c)) for c in range(wl.c_in)]
+    offs = conv_tap_offsets(wl.width)
+    keys = [hx.ckks_key_load(ctx, hx.from_host(uniform_residues((params.dnum, 2, M, N), q, name + "rk%d" % t)),
+                             hx.ckks_galois_element(ctx, off)) if off else None for t, off in enumerate(offs)]
+    q_mac = q[:level + 1] + q[params.num_q:]
+    masks = hx.from_host(uniform_residues((9, len(q_mac), N), q_mac, name + "masks"))
+    w_real = conv_weights(wl.c_out, wl.c_in, dist="he_normal").reshape(wl.c_out, wl.c_in, 9)
+    k = q[level] * 2.0 ** 10 / 2.0 ** 28
+    w_int = np.where(w_real >= 0, np.floor(w_real * k + 0.5), np.ceil(w_real * k - 0.5)).astype(np.int64)
+    w_res = hx.from_host(np.stack([np.mod(w_int, qi).astype(np.uint64) for qi in q_mac], axis=-1))
+    outs = [hx.empty(2, level, N) for _ in range(wl.c_out)]
+    mode = hx.HE_CONV_DEFERRED_MERGED
+    ws = torch.empty(hx.he_conv_workspace_bytes(ctx, wl.c_in, wl.c_out, wl.height, wl.width, wl.batch, level, mode), dtype=torch.uint8, device="cuda")
+    run = lambda: hx.he_conv_batched(ctx, wl.height, wl.width, wl.batch, level, ins, keys, masks, w_res, wl.c_out, outs=outs, ws=ws,
+                                     alignment=mode, weight_bits=hx.conv_weight_bits(w_int))
+    run()
+    torch.cuda.synchronize()
+    reps = 5
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        run()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / reps * 1e3
+    result["conv_" + name] = {"ms_per_layer": ms, "ms_per_image": ms / wl.batch, "c_in": wl.c_in, "c_out": wl.c_out,
+                              "image": "%dx%d" % (wl.height, wl.width), "batch": wl.batch, "limbs": params.num_q,
+                              "special_primes": params.num_p, "schedule": "deferred_merged"}
+
+
 def ntt_microbench(hx, torch, result):
     from workloads import CONFIGS, uniform_residues
     # NTT microbenchmark: 64 polynomials x 30 limbs at N = 2^16, forward then inverse
@@ -481,6 +518,8 @@ def main():
                              "staging_ms_hidden": alone * 1e3 + 2 * ms_per_step - both_dt * 1e3}
     del host_b, staged
     ntt_microbench(hx, torch, result)
+    # the convolution of the first ResNet-20 stage (16 -> 16 channels on 32 images of 32x32, 20 limbs + 7 special primes)
+    conv_microbench(hx, torch, "cfg4_resnet20_stage1", result)
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(wl, params, args.alignment, act_merged)
