@@ -207,7 +207,8 @@ typedef struct he_conv_desc {
                              holds w mod each modulus): weights are a real number times the weight scale, rounded, so
                              they are far narrower than a residue, and the multiply-accumulate then writes them in 3
                              (weight_bits <= 24) or 4 (<= 32) signed 8-bit digits instead of 7.  Same residues out;
-                             a weight beyond the promised bound gives wrong residues without an error. */
+                             a weight beyond the promised bound gives wrong residues without an error from
+                             he_conv_batched itself: he_conv_check_weights tests the promise. */
 } he_conv_desc;
 
 /* Workspace bytes he_conv_batched needs for this shape (0 on invalid arguments): the shared
@@ -217,6 +218,15 @@ size_t he_conv_workspace_bytes(const ckks_ctx* ctx, const he_conv_desc* desc);
 int he_conv_batched(const ckks_ctx* ctx, const he_conv_desc* desc, const uint64_t* const* h_d_in,
                     const ckks_key* const* rot_keys, const uint64_t* d_tap_masks, const uint64_t* d_w_res,
                     uint64_t* const* h_d_out, void* d_ws, size_t ws_bytes, void* stream);
+
+/* Tests the promise desc->weight_bits on the device-resident weights d_w_res of a layer (same layout and basis as
+ * he_conv_batched takes for desc->alignment): every residue must be the reduction of an integer w with
+ * |w| < 2^(weight_bits-1), i.e. lie in [0, 2^(weight_bits-1)) or in (q_i - 2^(weight_bits-1), q_i).  Returns CKKS_OK,
+ * or CKKS_ERR_INVALID_ARG with the number of offending residues in the error string.  weight_bits = 0 promises
+ * nothing and passes.  For set-up time, once per set of weights, not per layer evaluation: it waits for `stream`
+ * (one pass over d_w_res, one word read back) and, unlike every other call, must not be issued on one context from
+ * several host threads at once. */
+int he_conv_check_weights(const ckks_ctx* ctx, const he_conv_desc* desc, const uint64_t* d_w_res, void* stream);
 
 /* The accumulator of the optimised pipeline ("Optimized Inference Pipeline", the merge equation): g
  * down-sampled intermediate ciphertexts whose data occupy slots [0, sts) are cleaned, moved to
@@ -294,6 +304,19 @@ int he_fc_batched(const ckks_ctx* ctx, const he_fc_desc* desc, const uint64_t* d
 int he_poly_act_deg7(const ckks_ctx* ctx, const uint64_t* const* h_d_x, uint32_t n_ct, uint32_t level,
                      const int64_t* h_k, const ckks_key* rlk, int merged_division, uint64_t* const* h_d_out,
                      void* d_ws, size_t ws_bytes, void* stream);
+
+/* Self-test hook (not part of the paper's method): evaluates on the GPU the routines of the double-precision modular
+ * arithmetic that the transforms, basis conversions and fused inner products are made of, for moduli q < 2^50, on
+ * caller-given operands, so that a test can judge the device's results with wide integers.
+ *   CKKS_F64_MULMOD      out = y*w - q*c, c the integer nearest to y*wq      (d_wq[i] = d_w[i] / q rounded to nearest)
+ *   CKKS_F64_MULMOD_ANY  the same with c taken from the rounded product y*w  (d_wq unused)
+ *   CKKS_F64_REDUCE      out = y - q*round(y/q)                              (d_w, d_wq unused)
+ *   CKKS_F64_CANONICAL   out = y mod q in [0, q), through REDUCE             (d_w, d_wq unused)
+ *   CKKS_F64_CENTRE      out = y*w mod q as the centred residue, through MULMOD
+ * d_y int64[n] (integers, |y| < 2^51 for the products, < 2^53 otherwise), d_w uint64[n] in [0, q), d_out double[n]. */
+enum ckks_f64_op { CKKS_F64_MULMOD = 0, CKKS_F64_MULMOD_ANY = 1, CKKS_F64_REDUCE = 2, CKKS_F64_CANONICAL = 3, CKKS_F64_CENTRE = 4 };
+int ckks_f64mod_probe(int op, const int64_t* d_y, const uint64_t* d_w, const double* d_wq, uint64_t q, double* d_out, size_t n,
+                      void* stream);
 
 /* Optional per-kernel timing, for benchmarks (not part of the paper's method; callers that measure).
  * Between ckks_prof_begin and ckks_prof_end every launch of a kernel class whose bit is set in

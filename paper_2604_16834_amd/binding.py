@@ -43,7 +43,7 @@ EXPORTS = (
     "ckks_ctx_create", "ckks_ctx_destroy", "ckks_last_error_string", "ckks_workspace_bytes",
     "ckks_ntt_fwd", "ckks_ntt_inv", "ckks_key_load", "ckks_key_free", "ckks_galois_element",
     "ckks_keyswitch", "ckks_rotate_hoisted", "ckks_ptct_mac", "ckks_rescale", "ckks_ctct_mul_relin",
-    "he_conv_workspace_bytes", "he_conv_batched", "he_poly_act_deg7",
+    "he_conv_workspace_bytes", "he_conv_batched", "he_conv_check_weights", "he_poly_act_deg7", "ckks_f64mod_probe",
     "he_accumulator_workspace_bytes", "he_accumulator_merge", "he_fc_workspace_bytes", "he_fc_batched",
     "he_relayout_workspace_bytes", "he_relayout_two_rotations", "ckks_key_expand_a", "ckks_keyset_stage", "ckks_ctx_set_overlap",
     "ckks_prof_kernel_count", "ckks_prof_kernel_name", "ckks_prof_begin", "ckks_prof_end",
@@ -99,6 +99,8 @@ def _bind(path: str):
     lib.he_conv_workspace_bytes.argtypes = [vp, C.POINTER(_ConvDesc)]
     lib.he_conv_workspace_bytes.restype = sz
     lib.he_conv_batched.argtypes = [vp, C.POINTER(_ConvDesc), C.POINTER(vp), C.POINTER(vp), vp, vp, C.POINTER(vp), vp, sz, vp]
+    lib.he_conv_check_weights.argtypes = [vp, C.POINTER(_ConvDesc), vp, vp]
+    lib.ckks_f64mod_probe.argtypes = [i32, vp, vp, vp, C.c_uint64, vp, sz, vp]
     lib.he_poly_act_deg7.argtypes = [vp, C.POINTER(vp), u32, u32, C.POINTER(C.c_int64), vp, i32, C.POINTER(vp), vp, sz, vp]
     lib.he_accumulator_workspace_bytes.argtypes = [vp, u32, u32]
     lib.he_accumulator_workspace_bytes.restype = sz
@@ -143,8 +145,8 @@ def empty(*shape) -> torch.Tensor:
 def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
     if t is None:
         return None
-    if t.device.type != _expect_device or t.dtype not in (torch.int64, torch.uint64, torch.uint8) or not t.is_contiguous():
-        raise ValueError(f"need a contiguous int64 tensor on {_expect_device}")
+    if t.device.type != _expect_device or t.dtype not in (torch.int64, torch.uint64, torch.uint8, torch.float64) or not t.is_contiguous():
+        raise ValueError(f"need a contiguous int64 (float64 for the self-test hook) tensor on {_expect_device}")
     return t.data_ptr()
 
 
@@ -335,11 +337,41 @@ def conv_weight_bits(w_int) -> int:
     return m.bit_length() + 1
 
 
+def he_conv_check_weights(ctx: Context, c_in: int, c_out: int, level: int, w_res: torch.Tensor, weight_bits: int,
+                          alignment: int = HE_CONV_ALIGN_DIRECT, stream=None) -> None:
+    """Raises CkksError (CKKS_ERR_INVALID_ARG) if a residue of w_res breaks the promise weight_bits.  Waits for the stream."""
+    LM = level + 1 + ctx.num_p if alignment in (HE_CONV_DEFERRED_MODDOWN, HE_CONV_DEFERRED_MERGED) else level + 1
+    if w_res.numel() != c_out * c_in * 9 * LM:
+        raise ValueError("w_res must be [C_out][C_in][9][L], L = %d limbs" % LM)
+    d = _ConvDesc(c_in, c_out, 1, 1, 1, level, int(alignment), int(weight_bits))
+    ctx._check(_lib.he_conv_check_weights(ctx.handle, C.byref(d), _ptr(w_res), _stream(stream)))
+
+
+CKKS_F64_MULMOD, CKKS_F64_MULMOD_ANY, CKKS_F64_REDUCE, CKKS_F64_CANONICAL, CKKS_F64_CENTRE = range(5)
+
+
+def ckks_f64mod_probe(op: int, y: torch.Tensor, w: Optional[torch.Tensor], wq: Optional[torch.Tensor], q: int,
+                      out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """y int64[n], w int64[n] (uint64 residues bit for bit) or None, wq float64[n] or None -> float64[n]."""
+    n = y.numel()
+    if out is None:
+        out = torch.empty(n, dtype=torch.float64, device=y.device)
+    rc = _lib.ckks_f64mod_probe(int(op), _ptr(y), _ptr(w) if w is not None else None, _ptr(wq) if wq is not None else None, int(q), _ptr(out), n,
+                                _stream(stream))
+    if rc != CKKS_OK:
+        raise CkksError(rc, "ckks_f64mod_probe: invalid arguments")
+    return out
+
+
 def he_conv_batched(ctx: Context, height: int, width: int, batch: int, level: int, ins: Sequence[torch.Tensor],
                     rot_keys: Sequence[Optional[Key]], tap_masks: torch.Tensor, w_res: torch.Tensor, c_out: int,
                     outs: Optional[List[torch.Tensor]] = None, ws: Optional[torch.Tensor] = None, stream=None,
-                    alignment: int = HE_CONV_ALIGN_DIRECT, weight_bits: int = 0) -> List[torch.Tensor]:
+                    alignment: int = HE_CONV_ALIGN_DIRECT, weight_bits: int = 0, w_int_host=None,
+                    check_weights: bool = False) -> List[torch.Tensor]:
     """weight_bits: 0, or the promise |w| < 2^(weight_bits-1) for every integer weight (see conv_weight_bits).
+    A promise is tested before the layer runs when the caller gives the means: w_int_host (the integer weights as a host
+    array: compared with the bound here, ValueError) and / or check_weights=True (he_conv_check_weights on w_res: one more
+    pass over the device weights and a wait for the stream, CkksError).
     alignment: HE_CONV_ALIGN_DIRECT (eight hoisted rotations), HE_CONV_ALIGN_FOUR_KEYS (the paper's two-stage
     alignment with four keys), HE_CONV_DEFERRED_MODDOWN (one division by P per output channel) or
     HE_CONV_DEFERRED_MERGED (that division merged with the rescale).
@@ -361,6 +393,10 @@ def he_conv_batched(ctx: Context, height: int, width: int, batch: int, level: in
     for o in outs:
         if o.numel() != 2 * level * ctx.N:
             raise ValueError("each output must be [2][level][N]")
+    if weight_bits and w_int_host is not None and conv_weight_bits(w_int_host) > weight_bits:
+        raise ValueError("weight_bits = %d promised, but the weights need %d" % (weight_bits, conv_weight_bits(w_int_host)))
+    if weight_bits and check_weights:
+        he_conv_check_weights(ctx, c_in, c_out, level, w_res, weight_bits, alignment, stream)
     d = _ConvDesc(c_in, c_out, height, width, batch, level, int(alignment), int(weight_bits))
     ws = _ws(ctx, ws, he_conv_workspace_bytes(ctx, c_in, c_out, height, width, batch, level, alignment))
     ia = _ptr_array([_ptr(t) for t in ins])

@@ -1,29 +1,53 @@
-"""Builds libckks_mi355x.so in-tree with hipcc for gfx950 (cross-compiles without a GPU)."""
+"""Builds libckks_mi355x.so in-tree with hipcc for gfx950 (cross-compiles without a GPU): every source to an object
+file of its own, in parallel, then one link."""
 from __future__ import annotations
 
+import glob
 import os
 import subprocess
+from concurrent.futures import ThreadPoolExecutor
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
+OBJ = os.path.join(_HERE, "_build")
 OUT = os.path.join(_HERE, "libckks_mi355x.so")
-SOURCES = ["ntt.hip", "keyswitch.hip", "pointwise.hip", "wsum_mfma.hip", "keystage.hip", "context.cpp", "api.cpp"]
+SOURCES = ["ntt.hip", "keyswitch.hip", "pointwise.hip", "wsum_mfma.hip", "keystage.hip", "selftest.hip", "context.cpp", "api.cpp"]
 FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # keep the compiler from forming packed-fp32 instructions (no float math on this path anyway)
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
 ]
 
 
-def build(verbose: bool = False) -> str:
-    cmd = ["hipcc", *FLAGS, "-o", OUT, *[os.path.join(CSRC, s) for s in SOURCES]]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + res.stdout + res.stderr)
+
+
+def build(verbose: bool = False, incremental: bool = False) -> str:
+    """incremental: skip sources whose object file is newer than the source and every header (a convenience while
+    developing; the default compiles everything)."""
+    os.makedirs(OBJ, exist_ok=True)
+    headers = glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(_HERE, "..", "include", "*.h"))
+    newest_header = max(os.path.getmtime(h) for h in headers)
+    jobs = []
+    objs = []
+    for s in SOURCES:
+        src = os.path.join(CSRC, s)
+        obj = os.path.join(OBJ, s + ".o")
+        objs.append(obj)
+        if incremental and os.path.exists(obj) and os.path.getmtime(obj) > max(os.path.getmtime(src), newest_header):
+            continue
+        jobs.append(["hipcc", *FLAGS, "-c", "-o", obj, src])
+    with ThreadPoolExecutor(max_workers=min(8, max(1, len(jobs)))) as pool:
+        list(pool.map(lambda cmd: _run(cmd, verbose), jobs))
+    _run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", OUT, *objs], verbose)
     return OUT
 
 
 if __name__ == "__main__":
-    print(build(verbose=True))
+    import sys
+    print(build(verbose=True, incremental="--incremental" in sys.argv))

@@ -1191,6 +1191,27 @@ int ckks_ctct_mul_relin(const ckks_ctx* c, const uint64_t* d_a, const uint64_t* 
     return run_ctct(c, level, &a, cs, &b, cs, rlk->d_key, &out, 1, Arena(d_ws, ws_bytes), (hipStream_t)stream);
 }
 
+int he_conv_check_weights(const ckks_ctx* c, const he_conv_desc* d, const uint64_t* d_w_res, void* stream) {
+    if (!c) return CKKS_ERR_INVALID_ARG;
+    if (!d || !d_w_res) return set_err(c, CKKS_ERR_INVALID_ARG, "null pointer");
+    if (d->c_in == 0 || d->c_out == 0) return set_err(c, CKKS_ERR_INVALID_ARG, "empty convolution shape");
+    if (!level_ok(c, d->level)) return set_err(c, CKKS_ERR_LEVEL_MISMATCH, "level out of range");
+    if (d->alignment > HE_CONV_DEFERRED_MERGED) return set_err(c, CKKS_ERR_INVALID_ARG, "unknown alignment");
+    if (d->weight_bits == 0) return CKKS_OK;  // nothing promised
+    const bool ext = d->alignment == HE_CONV_DEFERRED_MODDOWN || d->alignment == HE_CONV_DEFERRED_MERGED;
+    hipStream_t st = (hipStream_t)stream;
+    HIP_TRY(launch_weight_check(c, d->level, ext, (const u64*)d_w_res, (size_t)d->c_out * d->c_in * 9, d->weight_bits, c->d_check, st));
+    u32 bad = 0;
+    HIP_TRY(hipMemcpyAsync(&bad, c->d_check, sizeof(bad), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    if (bad) {
+        c->err = std::to_string(bad) + " weight residues are not integers below 2^(weight_bits-1) = 2^" + std::to_string(d->weight_bits - 1) +
+                 " in magnitude: he_conv_batched would return wrong residues with this weight_bits";
+        return CKKS_ERR_INVALID_ARG;
+    }
+    return CKKS_OK;
+}
+
 int he_conv_batched(const ckks_ctx* c, const he_conv_desc* d, const uint64_t* const* h_d_in, const ckks_key* const* rot_keys,
                     const uint64_t* d_tap_masks, const uint64_t* d_w_res, uint64_t* const* h_d_out, void* d_ws, size_t ws_bytes,
                     void* stream) {

@@ -79,6 +79,7 @@ extern "C" void ckks_ctx_destroy(ckks_ctx* c) {
     (void)hipFree(c->d_rescale_ep);
     (void)hipFree(c->d_moddown_rs_prep_f);
     (void)hipFree(c->d_rescale);
+    (void)hipFree(c->d_check);
     if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
     if (c->ev_join) (void)hipEventDestroy(c->ev_join);
     if (c->side) (void)hipStreamDestroy(c->side);
@@ -379,6 +380,7 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
     if (e == hipSuccess) e = upload(moddown_prep_f, &c->d_moddown_prep_f);
     if (e == hipSuccess) e = upload(moddown_rs_prep_f, &c->d_moddown_rs_prep_f);
     if (e == hipSuccess) e = upload(resc, &c->d_rescale);
+    if (e == hipSuccess) e = hipMalloc((void**)&c->d_check, 256);
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
         g_create_error = std::string("HIP error while building tables: ") + hipGetErrorString(e);

@@ -6,6 +6,7 @@
 #include <vector>
 
 #include "../../include/ckks.h"
+#include "f64mod.h"
 #include "modarith.h"
 
 #define CKKS_MAX_MODULI 64
@@ -26,10 +27,7 @@ struct __attribute__((aligned(16))) TwPair {
     u64 w, s;
 };
 
-// the same for the double-precision butterflies: the twiddle as a double and twiddle / q rounded to nearest
-struct __attribute__((aligned(16))) TwF {
-    double w, wq;
-};
+// the same for the double-precision butterflies: TwF (f64mod.h), the twiddle as a double and twiddle / q rounded to nearest
 // per-modulus constants of the double-precision butterflies
 struct ModConstF {
     double q, qinv;        // the modulus and 1/q rounded to nearest
@@ -140,6 +138,7 @@ struct ckks_ctx {
     u64* d_moddown = nullptr;         // phat_inv[k_pad], phat_inv_sh[k_pad], phat_q[num_q][k_pad], pinv[num_q], pinv_sh[num_q], negp[num_q]
     u64* d_moddown_rs = nullptr;      // per level l >= 1, the same layout (k_pad -> k2_pad) for the dropped set {q_l, p_0..p_{k-1}}:
                                       // ModDown and rescale as one division by P*q_l; see moddown_rs_table()
+    u32* d_check = nullptr;           // one word: the violation count of he_conv_check_weights
     u64* d_rescale = nullptr;         // [num_q][num_q][3]: (q_l^-1 mod q_i, its Shoup companion, q_l mod q_i)
     // The conversion constants once more as doubles (w, w / q_target), for the double-precision base conversions that
     // contexts with ntt_f64 use: same row layout as the integer tables, one TwF per entry.
@@ -295,6 +294,8 @@ hipError_t launch_key_expand_a(const ckks_ctx* c, u64 seed, u64* key, hipStream_
 hipError_t launch_add_plain(const ckks_ctx* c, u32 level, const u64* pt, u64* ct, hipStream_t st);
 hipError_t launch_ct_sum(const ckks_ctx* c, u32 level, const PtrList8& items, u32 n, u64* out, hipStream_t st, bool extended = false);
 hipError_t launch_centre_ext(const ckks_ctx* c, u32 level, const u64* mask, const u64* ct, u64* xs, XLayout xl, u32 k, hipStream_t st);
+hipError_t launch_weight_check(const ckks_ctx* c, u32 level, bool extended, const u64* w_res, size_t n_w, u32 weight_bits, u32* d_count,
+                               hipStream_t st);
 size_t weighted_sum_scratch_elems(const ckks_ctx* c, u32 n_limbs, u32 n_terms, u32 c_out);
 // weight_bits: the caller's bound |w| < 2^(weight_bits - 1) on the integers behind w_res (0 = none)
 hipError_t launch_weighted_sum(const ckks_ctx* c, u32 level, bool extended, const u64* xs, XLayout xl, u32 n_terms, const u64* w_res,

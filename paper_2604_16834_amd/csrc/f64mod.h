@@ -1,29 +1,97 @@
-// Exact modular arithmetic on integers held in doubles, for moduli below 2^50 (device code only).
-// y * w - q * round(y * w / q) is computed without rounding error from the rounded product h = y*w, its exact error
-// l = fma(y, w, -h), and the quotient c = the integer nearest to y * (w / q): fma(-c, q, h) + l, of magnitude below
-// 0.63 q.  Needs |y| < 2^51, 0 <= w < q < 2^50, wq = w / q rounded to nearest.  Sums of such terms stay exact below 2^53.
+// Exact modular arithmetic on integers held in doubles, for moduli below 2^50.
+//
+// This is the one copy of the arithmetic that the double-precision butterflies, the basis conversions inside the
+// transforms and the fused inner products are made of.  It has no dependency but <stdint.h> and compiles for the GPU
+// (hipcc) and for the host (any C++ compiler, with floating-point contraction switched off: -ffp-contract=off), so that
+// a CPU test can compare every routine with 128-bit integer arithmetic on boundary values and on random ones.
+//
+//   y * w - q * round(y * w / q) is computed without rounding error from the rounded product h = y*w, its exact error
+//   l = fma(y, w, -h), and a quotient c that is an integer within 3/4 of y*w/q:  fma(-c, q, h) + l.
+//   The quotient comes from y * (w / q) when w / q is precomputed (a twiddle, a conversion constant: mulmod), or from
+//   h * (1 / q) when the multiplier is data (a key word, a ciphertext residue: mulmod_any).  Adding 1.5 * 2^52 inside a
+//   fused multiply-add rounds the exact product to the nearest integer, so c is off by at most 1/2 plus the error of the
+//   factor w / q (relative 2^-53) or of h and 1 / q (relative 2^-53 each).
+// Bounds (q < 2^50, all values integers):
+//   mulmod      |y| < 2^51, 0 <= w < q, wq = w / q rounded to nearest   ->  |result| <= (1/2 + |y| / 2^53) q  < 3/4 q
+//   mulmod_any  |y| < q,    0 <= w < q, qinv = 1 / q rounded to nearest ->  |result| <= (1/2 + |y| / 2^52) q  < 3/4 q
+//   reduce      |v| < 2^53                                              ->  |result| <= q/2 + 1
+// (for reduced multiplicands, |y| <= q/2 + 1: below 0.57 q and 0.63 q).  h - c q is an integer below 2^51 and l one below
+// 2^48, so the last two operations are exact.  A sum of up to eight products stays below 2^53 and is exact, and three
+// forward butterfly stages after a reduce keep every multiplicand below 2q + 1 < 2^51.
 #pragma once
-#include "ctx.h"
+#include <stdint.h>
 
+#if defined(__HIPCC__)
+#include <hip/hip_runtime.h>
+#define F64M_FN __host__ __device__ __forceinline__
 #pragma clang fp contract(off)  // every product and sum as written
+#else
+#define F64M_FN static inline
+#endif
 
 #define F64M_MAGIC 6755399441055744.0  // 1.5 * 2^52: adding it rounds to the nearest integer (magnitudes below 2^51)
 #define F64M_2P52 4503599627370496.0
 
-__device__ __forceinline__ double f64m_mulmod(double y, double w, double wq, double q) {
+// a constant multiplier as a double with its quotient by the modulus (w / q rounded to nearest), one 16-byte word
+struct __attribute__((aligned(16))) TwF {
+    double w, wq;
+};
+
+F64M_FN double f64m_bits_to_double(uint64_t b) {
+    double d;
+    __builtin_memcpy(&d, &b, 8);
+    return d;
+}
+F64M_FN uint64_t f64m_double_to_bits(double d) {
+    uint64_t b;
+    __builtin_memcpy(&b, &d, 8);
+    return b;
+}
+
+// the integer nearest to v * c (|v * c| < 2^51), from the exact product: one rounding only
+F64M_FN double f64m_round_mul(double v, double c) { return __builtin_fma(v, c, F64M_MAGIC) - F64M_MAGIC; }
+
+// v - q * round(v / q) for an integer |v| < 2^53: magnitude at most q/2 + 1
+F64M_FN double f64m_reduce(double v, double q, double qinv) { return __builtin_fma(-f64m_round_mul(v, qinv), q, v); }
+
+// y * w - q * c with c the integer nearest to y * wq
+F64M_FN double f64m_mulmod(double y, double w, double wq, double q) {
     const double h = y * w;
     const double l = __builtin_fma(y, w, -h);
-    const double c = __builtin_fma(y, wq, F64M_MAGIC) - F64M_MAGIC;
+    const double c = f64m_round_mul(y, wq);
     return __builtin_fma(-c, q, h) + l;
 }
-// v - q * round(v / q) for an integer |v| < 2^53: magnitude at most q/2 + 1
-__device__ __forceinline__ double f64m_reduce(double v, double q, double qinv) {
-    return __builtin_fma(-(__builtin_fma(v, qinv, F64M_MAGIC) - F64M_MAGIC), q, v);
+
+// the same for a multiplier without a precomputed w / q: the quotient comes from the rounded product
+F64M_FN double f64m_mulmod_any(double y, double w, double q, double qinv) {
+    const double h = y * w;
+    const double l = __builtin_fma(y, w, -h);
+    const double c = f64m_round_mul(h, qinv);
+    return __builtin_fma(-c, q, h) + l;
 }
-// a residue below 2^52 as a double, through the mantissa of 2^52 + v
-__device__ __forceinline__ double f64m_from_u64(u64 v) { return __longlong_as_double((long long)(v | 0x4330000000000000ull)) - F64M_2P52; }
-// |v| <= q/2 + 1 -> the canonical residue in [0, q)
-__device__ __forceinline__ u64 f64m_canonical(double v, double q) {
-    const double p = v < 0.0 ? v + q : v;
-    return (u64)__double_as_longlong(p + F64M_2P52) & 0x000fffffffffffffull;
+
+// canonical residues below 2^52 <-> doubles through the mantissa of 2^52 + v
+F64M_FN double f64m_from_u64(uint64_t v) { return f64m_bits_to_double(v | 0x4330000000000000ull) - F64M_2P52; }
+F64M_FN uint64_t f64m_to_u64(double v) { return f64m_double_to_bits(v + F64M_2P52) & 0x000fffffffffffffull; }
+
+// |v| <= q/2 + 1 (more generally -q <= v < q) -> the canonical residue in [0, q)
+F64M_FN uint64_t f64m_canonical(double v, double q) { return f64m_to_u64(v < 0.0 ? v + q : v); }
+
+// |t| < q (the result of a product) -> the centred representative in (-q/2, q/2); q is odd: no residue on the boundary
+F64M_FN double f64m_centre(double t, double q) {
+    const double half = 0.5 * q;
+    return t > half ? t - q : (t < -half ? t + q : t);
+}
+
+// sum_{a < ND} y[a] * cw[a].w  mod q  (|y[a]| < 2^51) as a reduced double: the basis-conversion sum.  Partial sums of at
+// most eight products stay below 2^53; longer rows are reduced once on the way.
+template <int ND>
+F64M_FN double f64m_dot(const double* y, const TwF* cw, double q, double qinv) {
+    double s = 0.0;
+#pragma unroll
+    for (int a = 0; a < ND; a++) {
+        s += f64m_mulmod(y[a], cw[a].w, cw[a].wq, q);
+        if (a == 7 && ND > 8) s = f64m_reduce(s, q, qinv);
+    }
+    return f64m_reduce(s, q, qinv);
 }

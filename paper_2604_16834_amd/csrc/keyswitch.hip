@@ -135,13 +135,7 @@ __global__ __launch_bounds__(KS_THREADS) void modup_conv_f64_kernel(const u64* _
         if (t >= lo && t < lo + nd) continue;  // the digit's own limbs are read from the polynomial itself (DigitSrc)
         const TwF* ce = (const TwF*)__builtin_assume_aligned(convf + (size_t)e * AP, 16 * AP);
         const double q = mcf[t].q, qinv = mcf[t].qinv;
-        double s = 0.0;
-#pragma unroll
-        for (u32 a = 0; a < AP; a++) {
-            s += f64m_mulmod(yd[a], ce[a].w, ce[a].wq, q);
-            if (a == 7 && AP > 8) s = f64m_reduce(s, q, qinv);  // keeps longer sums below 2^53
-        }
-        digit[(size_t)e * N + x] = f64m_canonical(f64m_reduce(s, q, qinv), q);
+        digit[(size_t)e * N + x] = f64m_canonical(f64m_dot<AP>(yd, ce, q, qinv), q);
     }
 }
 
@@ -676,13 +670,7 @@ __global__ __launch_bounds__(KS_THREADS) void moddown_conv_f64_kernel(const u64*
     for (u32 i = i0; i < i0 + lpb && i < n_out; i++) {
         const TwF* pe = phf + (size_t)i * KP;
         const double q = mcf[i].q, qinv = mcf[i].qinv;
-        double s = 0.0;
-#pragma unroll
-        for (u32 a = 0; a < KR; a++) {
-            s += f64m_mulmod(z[a], pe[a].w, pe[a].wq, q);
-            if (a == 7 && KR > 8) s = f64m_reduce(s, q, qinv);
-        }
-        w[((size_t)comp * n_out + i) * N + x] = f64m_canonical(f64m_reduce(s, q, qinv), q);
+        w[((size_t)comp * n_out + i) * N + x] = f64m_canonical(f64m_dot<KR>(z, pe, q, qinv), q);
     }
 }
 

@@ -22,7 +22,7 @@
 //   ArithF64  every modulus below 2^50: residues are integers held in doubles and the twiddle product is
 //             reduced with fused multiply-adds: for |y| < 2^51, h = y*w rounded, l = fma(y, w, -h) its
 //             exact error, c = the integer nearest to y*(w/q) (one fma against 1.5*2^52), and
-//             fma(-c, q, h) + l = y*w - c*q exactly, of magnitude below 0.63 q: six double-precision
+//             fma(-c, q, h) + l = y*w - c*q exactly, of magnitude below 0.75 q: six double-precision
 //             operations where the integer path spends more than twenty 32-bit ones, which moves the
 //             lo pass from instruction issue to the HBM roof.  Values are brought back to |v| <= q/2 + 1
 //             (three operations) after every round of at most three forward stages and after every sum of
@@ -32,9 +32,8 @@
 #include <type_traits>
 
 #include "ctx.h"
+#include "f64mod.h"
 #include "galois.h"
-
-#pragma clang fp contract(off)  // the error-free transformations below need every product and sum as written
 
 #define NTT_THREADS 256
 #define NTT_TILE 2048
@@ -70,38 +69,22 @@ struct ArithU64 {
     static __device__ __forceinline__ void fwd_round_end(E*, const MC&) {}
 };
 
-// ---- double-precision arithmetic for moduli below 2^50 -----------------------------------------------------
-#define F64_MAGIC 6755399441055744.0  // 1.5 * 2^52: adding it rounds to the nearest integer (for magnitudes below 2^51)
-#define F64_2P52 4503599627370496.0
+// ---- double-precision arithmetic for moduli below 2^50 (the routines themselves: f64mod.h) -----------------------
 struct ArithF64 {
     typedef double E;
     typedef TwF TW;
     typedef ModConstF MC;
-    // the integer nearest to v * c (|v * c| < 2^51), from the exact product: one rounding only
-    static __device__ __forceinline__ double round_mul(double v, double c) { return __builtin_fma(v, c, F64_MAGIC) - F64_MAGIC; }
+    static __device__ __forceinline__ double round_mul(double v, double c) { return f64m_round_mul(v, c); }
     // v - q * round(v / q): |result| <= q/2 + 1 for integer |v| < 2^53
-    static __device__ __forceinline__ double reduce(double v, const MC& m) { return __builtin_fma(-round_mul(v, m.qinv), m.q, v); }
-    // y * w - q * round(y * w / q), exact, magnitude below 0.63 q; needs |y| < 2^51, 0 <= w < q, wq = w / q rounded
-    static __device__ __forceinline__ double mulmod(double y, double w, double wq, double q) {
-        const double h = y * w;
-        const double l = __builtin_fma(y, w, -h);
-        const double c = round_mul(y, wq);
-        return __builtin_fma(-c, q, h) + l;
-    }
-    // the same for a multiplier without a precomputed w / q (a key word, a ciphertext residue): the quotient comes from
-    // the rounded product, |y| < q, 0 <= w < q; exact, magnitude below 0.57 q (host check against 128-bit integers)
-    static __device__ __forceinline__ double mulmod_any(double y, double w, double q, double qinv) {
-        const double h = y * w;
-        const double l = __builtin_fma(y, w, -h);
-        const double c = round_mul(h, qinv);
-        return __builtin_fma(-c, q, h) + l;
-    }
-    // canonical residues below 2^52 <-> doubles through the mantissa of 2^52 + v
-    static __device__ __forceinline__ double from_u64(u64 raw) { return __longlong_as_double((long long)(raw | 0x4330000000000000ull)) - F64_2P52; }
-    static __device__ __forceinline__ u64 to_u64(double v) { return (u64)__double_as_longlong(v + F64_2P52) & 0x000fffffffffffffull; }
-    static __device__ __forceinline__ u64 canonical(double v, const MC& m) {  // |v| <= q/2 + 1 -> [0, q)
-        return to_u64(v < 0.0 ? v + m.q : v);
-    }
+    static __device__ __forceinline__ double reduce(double v, const MC& m) { return f64m_reduce(v, m.q, m.qinv); }
+    // y * w - q * c, c an integer within 3/4 of y * w / q: exact, magnitude below 0.75 q; needs |y| < 2^51, 0 <= w < q, wq = w / q rounded
+    static __device__ __forceinline__ double mulmod(double y, double w, double wq, double q) { return f64m_mulmod(y, w, wq, q); }
+    // the same for a multiplier without a precomputed w / q (a key word, a ciphertext residue): |y| < q, 0 <= w < q;
+    // exact, magnitude below 0.75 q (0.63 q for |y| <= q/2 + 1)
+    static __device__ __forceinline__ double mulmod_any(double y, double w, double q, double qinv) { return f64m_mulmod_any(y, w, q, qinv); }
+    static __device__ __forceinline__ double from_u64(u64 raw) { return f64m_from_u64(raw); }
+    static __device__ __forceinline__ u64 to_u64(double v) { return f64m_to_u64(v); }
+    static __device__ __forceinline__ u64 canonical(double v, const MC& m) { return f64m_canonical(v, m.q); }  // |v| <= q/2 + 1 -> [0, q)
     static __device__ __forceinline__ E load_first(u64 raw, const MC& m, bool) { return reduce(from_u64(raw), m); }
     static __device__ __forceinline__ E load_mid(u64 raw) { return __longlong_as_double((long long)raw); }
     static __device__ __forceinline__ u64 store_mid(E v) { return (u64)__double_as_longlong(v); }
@@ -417,7 +400,7 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_div_kernel(NttArgs arg
 // comes out, adds the product of the digit that owns e (its limb is the decomposed polynomial's own, never transformed)
 // and, on the q-limbs, P times the optional addends, and stores the two components of the inner product: the extended
 // digits are never written in evaluation form nor read back.  All sums are exact integers in doubles (at most
-// beta + 1 terms below 0.57 q each).
+// beta + 1 terms below 0.75 q each).
 struct MacEpilogue {
     DigitSrc D;           // D.digits: rows (j*E + e) hold the hi pass' output (doubles); D.own: the decomposed polynomials
     PtrList8 key;         // per batch item: [dnum][2][M][N] (the same pointer for a shared key)
@@ -544,7 +527,7 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_mac_kernel(NttArgs arg
             double dd1 = A::mulmod_any(A0, B1, mc.q, mc.qinv) + A::mulmod_any(A1, B0, mc.q, mc.qinv);
             if (c0) dd0 += A::from_u64(c0[po + x]);
             if (c1) dd1 += A::from_u64(c1[po + x]);
-            if (lx) {  // at most 0.57 q more per term: both sums stay below 2^52
+            if (lx) {  // at most 0.75 q more per term: both sums stay below 2^53
                 dd0 += A::mulmod_any(A::from_u64(lx[x]), ka, mc.q, mc.qinv) + A::mulmod_any(A::from_u64(ly[x]), kb, mc.q, mc.qinv);
                 dd1 += A::mulmod_any(A::from_u64(lx[ep.x_cstride + x]), ka, mc.q, mc.qinv) +
                        A::mulmod_any(A::from_u64(ly[ep.y_cstride + x]), kb, mc.q, mc.qinv);
@@ -768,13 +751,8 @@ __device__ __forceinline__ void conv_load(double (&yv)[AP], const double* __rest
 }
 template <int AP, int ND>
 __device__ __forceinline__ double conv_sum(const double (&yv)[AP], const TwF* cw, double q, double qinv) {
-    double s = 0.0;
-#pragma unroll
-    for (int a = 0; a < ND; a++) {
-        s += ArithF64::mulmod(yv[a], cw[a].w, cw[a].wq, q);
-        if (a == 7 && AP > 8) s = __builtin_fma(-ArithF64::round_mul(s, qinv), q, s);  // keeps longer sums below 2^53
-    }
-    return __builtin_fma(-ArithF64::round_mul(s, qinv), q, s);
+    static_assert(ND <= 8 || AP > 8, "rows of more than eight entries are padded to twelve or sixteen");
+    return f64m_dot<ND>(yv, cw, q, qinv);
 }
 
 // One workgroup converts and transforms the same tile of T target limbs: the source residues are fetched once for all T
@@ -858,15 +836,13 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_hi_conv_kernel(NttArgs ar
 }
 
 // The inverse transform's last store: times 1/N, canonical; or (double-precision arithmetic only) times *scale and centred,
-// as a double: |t| < 0.63 q after the exact product, so the centred representative is t, t - q or t + q.
+// as a double: |t| < 0.75 q after the exact product, so the centred representative is t, t - q or t + q.
 template <class A>
 __device__ __forceinline__ u64 inv_last_store(typename A::E v, const typename A::MC& m, const TwF* scale) {
     if constexpr (std::is_same<A, ArithF64>::value) {
         if (scale) {
             const TwF k = *scale;
-            double t = ArithF64::mulmod(v, k.w, k.wq, m.q);
-            const double half = 0.5 * m.q;  // q is odd: no residue sits on the boundary
-            t = t > half ? t - m.q : (t < -half ? t + m.q : t);
+            const double t = f64m_centre(ArithF64::mulmod(v, k.w, k.wq, m.q), m.q);
             return (u64)__double_as_longlong(t);
         }
     }

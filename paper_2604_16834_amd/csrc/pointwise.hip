@@ -5,13 +5,9 @@
 // ("Other Layers").  All of them stream HBM once; coefficients x are the fastest index so every
 // wavefront touches contiguous 512-byte runs.
 #include "ctx.h"
+#include "galois.h"
 
 #define PW_THREADS 256
-
-__device__ __forceinline__ u32 pw_gather_index(u32 k, u32 g, u32 log_n) {
-    u32 e = ((2u * (__brev(k) >> (32 - log_n)) + 1u) * g) & ((2u << log_n) - 1u);
-    return __brev((e - 1u) >> 1) >> (32 - log_n);
-}
 
 // out[p][k] = in[p][pi_g(k)] for n_polys limb-polys (the same gather for every modulus)
 __global__ __launch_bounds__(PW_THREADS) void automorph_kernel(const u64* __restrict__ in, u64* __restrict__ out, u32 log_n, u32 g) {
@@ -19,7 +15,7 @@ __global__ __launch_bounds__(PW_THREADS) void automorph_kernel(const u64* __rest
     const u32 x = blockIdx.x * PW_THREADS + threadIdx.x;
     if (x >= N) return;
     const size_t base = (size_t)blockIdx.y * N;
-    out[base + x] = in[base + pw_gather_index(x, g, log_n)];
+    out[base + x] = in[base + galois_gather_index(x, g, log_n)];
 }
 
 hipError_t launch_automorph(const ckks_ctx* c, u32 n_polys, const u64* in, u32 g, u64* out, hipStream_t st) {
@@ -453,5 +449,30 @@ hipError_t launch_lincomb2(const ckks_ctx* c, u32 level, const PtrList8& a, size
     ProfScope ps__(c, K_LINCOMB2, st, 16.0 * n * c->N * (level + 1.0) * (3.0 + (add ? 1.0 : 0.0)), 4.0 * n * c->N * (level + 1.0));
     hipLaunchKernelGGL(lincomb2_kernel, grid, dim3(PW_THREADS), 0, st, a, a_cstride, b, b_cstride, add, add_bstride, K, out, out_bstride,
                        c->d_mc, c->N, level);
+    return hipGetLastError();
+}
+
+// ---- the weight-width promise of the convolution (he_conv_desc.weight_bits), tested on the device-resident weights ----------
+// w_res [n_w][nl]: counts the residues outside [0, bound) and (q - bound, q), bound = 2^(weight_bits - 1)
+__global__ __launch_bounds__(PW_THREADS) void weight_check_kernel(const u64* __restrict__ w_res, const ModConst* __restrict__ mc, size_t n_w,
+                                                                  u32 nl, u32 level, u32 num_q, u64 bound, u32* __restrict__ bad) {
+    const size_t idx = (size_t)blockIdx.x * PW_THREADS + threadIdx.x;
+    if (idx >= n_w * nl) return;
+    const u32 e = (u32)(idx % nl);
+    const u64 q = mc[e <= level ? e : num_q + (e - level - 1)].q;
+    const u64 v = w_res[idx];
+    const bool ok = v < q && (v < bound || q - v < bound);
+    if (!ok) atomicAdd(bad, 1u);
+}
+__global__ void clear_word_kernel(u32* p) { *p = 0; }
+
+hipError_t launch_weight_check(const ckks_ctx* c, u32 level, bool extended, const u64* w_res, size_t n_w, u32 weight_bits, u32* d_count,
+                               hipStream_t st) {
+    const u32 nl = extended ? c->ext_limbs(level) : level + 1;
+    const u64 bound = weight_bits >= 64 ? ~0ull : 1ull << (weight_bits - 1);
+    hipLaunchKernelGGL(clear_word_kernel, dim3(1), dim3(1), 0, st, d_count);
+    const size_t total = n_w * nl;
+    hipLaunchKernelGGL(weight_check_kernel, dim3((unsigned)((total + PW_THREADS - 1) / PW_THREADS)), dim3(PW_THREADS), 0, st, w_res, c->d_mc,
+                       n_w, nl, level, c->num_q, bound, d_count);
     return hipGetLastError();
 }

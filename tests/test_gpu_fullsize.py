@@ -99,16 +99,34 @@ def test_cfg4_resnet20_stage1_conv():
     want = orc.he_conv(cts, level, wl.width, keys, masks, w_int, out_channels=sampled)
     for o in sampled:
         assert np.array_equal(outs[o], want[o]), f"output channel {o}"
+    # the schedule the benchmark times at this shape: one division by P * q_level per output, weight bound stated
+    print("cfg4: deferred schedule with merged division", flush=True)
+    masks_ext, w_int_ext = orc.conv_operands_ext(w, wl.height, wl.width, wl.batch, level, 2.0 ** 28, p.moduli[level] / 2.0 ** 28)
+    assert np.array_equal(w_int_ext, w_int)
+    ext_moduli = [p.moduli[t] for t in orc.ext_moduli_idx(level)]
+    outs_m = hx.he_conv_batched(ctx, wl.height, wl.width, wl.batch, level, [hx.from_host(c) for c in cts], dkeys, hx.from_host(masks_ext),
+                                hx.from_host(w_residues(w_int, ext_moduli, len(ext_moduli) - 1)), wl.c_out,
+                                alignment=hx.HE_CONV_DEFERRED_MERGED, weight_bits=hx.conv_weight_bits(w_int), w_int_host=w_int,
+                                check_weights=True)
+    outs_m = [hx.to_host(o) for o in outs_m]
+    worst = 0.0
+    for o in range(wl.c_out):
+        dec = orc.unpack_channel(orc.decrypt(outs_m[o], level - 1, s_ntt, 2.0 ** 40), wl.batch, wl.height, wl.width)
+        worst = max(worst, float(np.abs(dec - ref[:, o]).max()))
+    assert worst < 1e-4, worst
+    want = orc.he_conv_deferred(cts, level, wl.width, keys, masks_ext, w_int, out_channels=sampled, merged=True)
+    for o in sampled:
+        assert np.array_equal(outs_m[o], want[o]), f"output channel {o}, deferred schedule with merged division"
 
 
 def test_cfg5_resnet20_stage3_block_slice():
     """64 -> 64 channels on 8x8 images, batch 512, 24 limbs + 8 special primes, then the degree-7
-    activation on all 64 channels: the launch configuration bench.py times.  The oracle cannot
-    afford the 512 rotations, so: every conv output (deferred schedule with merged division, as timed) decrypted
+    activation on all 64 channels: the launch configuration bench.py times.  The oracle affords the
+    512 inner products but not all 64 x 576 multiply-accumulates, so: every conv output (deferred schedule with merged division, as timed) decrypted
     against the float64 convolution (1e-4) and every activation output against the float64 polynomial
     (1e-3); limb-for-limb parity of the activation on sampled channels (computed by the oracle from the
-    GPU's conv output), and of the whole conv, in the direct and in the deferred schedule, on an 8 -> 3
-    channel slice of the same shape."""
+    GPU's conv output), of two output channels of the full 64 -> 64 convolution in the timed schedule, and of the
+    whole conv, in the direct and in the deferred schedule, on an 8 -> 3 channel slice of the same shape."""
     wl = CONFIGS["cfg5_resnet20_stage3"]
     p = wl.params()
     orc, ctx = Oracle(p), hx.Context(p)
@@ -135,6 +153,15 @@ def test_cfg5_resnet20_stage3_block_slice():
     for o in range(wl.c_out):
         assert torch.equal(conv[o], wide[o]), f"output channel {o}: four-digit and seven-digit weights disagree"
     del wide
+    # two output channels of the real 64 -> 64 layer, one from each 32-channel output tile, limb for limb: the oracle aligns all
+    # 64 inputs (about a second each) and sums the 576 terms of the two outputs
+    print("cfg5: oracle on two output channels of the 64 -> 64 layer", flush=True)
+    sampled = (9, 50)
+    want = orc.he_conv_deferred(cts, level, wl.width, keys, masks_ext, w_int, out_channels=sampled, merged=True)
+    for o in sampled:
+        assert np.array_equal(hx.to_host(conv[o]), want[o]), f"output channel {o} of the full layer"
+    del want
+    print("cfg5: activation", flush=True)
     scale = 2.0 ** 50
     plan = orc.act_schedule(level - 1, scale)
     d_rlk = hx.ckks_key_load(ctx, hx.from_host(rlk), 0)

@@ -287,6 +287,75 @@ def test_he_conv_deferred_merged_division_matches_oracle(name, level, bits):
         assert np.abs(dec - ref[:, o]).max() < 1e-4
 
 
+@pytest.mark.parametrize("mask_bits", [28, 20], ids=["w24", "w32"])
+def test_he_conv_64_input_channels_in_the_timed_schedule(mask_bits):
+    """64 -> 40 channels: 576 terms, the multiply-accumulate's regular instantiation (whole 64-term blocks, term-innermost
+    operand layout, both output tiles, nine blocks through the double-buffered pipeline) in the deferred schedule with the
+    merged division, as the block-slice benchmark runs it: every residue of every output against the oracle, with the
+    weight bound stated (three signed digits for the 2^28 mask scale, four for 2^20) and without it (seven)."""
+    wl = CONFIGS["small_conv_c64"]
+    p = wl.params()
+    orc, ctx = both(p)
+    level = p.num_q - 1
+    s, s_ntt = orc.gen_secret(901)
+    img = image_batch(wl.batch, wl.c_in, wl.height, wl.width)
+    w = conv_weights(wl.c_out, wl.c_in)
+    scale = 2.0 ** 40
+    cts = [orc.encrypt(orc.pack_channel(img, c), scale, level, s_ntt, 910 + c) for c in range(wl.c_in)]
+    offs = conv_tap_offsets(wl.width)
+    keys = {off: orc.gen_rotation_key(s, s_ntt, off, 990 + i) for i, off in enumerate(offs) if off}
+    masks, w_int = orc.conv_operands_ext(w, wl.height, wl.width, wl.batch, level, 2.0 ** mask_bits, p.moduli[level] / 2.0 ** mask_bits)
+    wb = hx.conv_weight_bits(w_int)
+    assert (16 < wb <= 24) if mask_bits == 28 else (24 < wb <= 32), wb
+    ext_moduli = [p.moduli[t] for t in orc.ext_moduli_idx(level)]
+    dkeys = [hx.ckks_key_load(ctx, hx.from_host(keys[off]), hx.ckks_galois_element(ctx, off)) if off else None for off in offs]
+    d_cts = [hx.from_host(c) for c in cts]
+    d_masks, d_w = hx.from_host(masks), hx.from_host(w_residues(w_int, ext_moduli, len(ext_moduli) - 1))
+    want = orc.he_conv_deferred(cts, level, wl.width, keys, masks, w_int, merged=True)
+    ref = conv2d_reference(img, w)
+    for bits in (wb, 0):
+        outs = hx.he_conv_batched(ctx, wl.height, wl.width, wl.batch, level, d_cts, dkeys, d_masks, d_w, wl.c_out,
+                                  alignment=hx.HE_CONV_DEFERRED_MERGED, weight_bits=bits, w_int_host=w_int, check_weights=True)
+        for o in range(wl.c_out):
+            got = hx.to_host(outs[o])
+            assert np.array_equal(got, want[o]), f"output channel {o}, weight_bits {bits}"
+            dec = orc.unpack_channel(orc.decrypt(got, level - 1, s_ntt, scale), wl.batch, wl.height, wl.width)
+            assert np.abs(dec - ref[:, o]).max() < 1e-4
+
+
+def test_weight_bound_is_checked_when_asked():
+    """A weight beyond the stated bound is rejected by the host check (integer weights given) and by the device check
+    (residues only), instead of silently giving wrong residues; weights inside the bound, negative ones included, pass."""
+    wl, p, orc, level, s_ntt, img, w, scale, cts, keys, masks, w_int, outs = conv_case("small_conv", deferred=True, merged=True, narrow=True)
+    ctx = hx.Context(p)
+    ext_moduli = [p.moduli[t] for t in orc.ext_moduli_idx(level)]
+    wb = hx.conv_weight_bits(w_int)
+    d_w = hx.from_host(w_residues(w_int, ext_moduli, len(ext_moduli) - 1))
+    hx.he_conv_check_weights(ctx, wl.c_in, wl.c_out, level, d_w, wb, hx.HE_CONV_DEFERRED_MERGED)
+    hx.he_conv_check_weights(ctx, wl.c_in, wl.c_out, level, d_w, 0, hx.HE_CONV_DEFERRED_MERGED)      # no promise: nothing to test
+    with pytest.raises(hx.CkksError) as e:
+        hx.he_conv_check_weights(ctx, wl.c_in, wl.c_out, level, d_w, wb - 1, hx.HE_CONV_DEFERRED_MERGED)
+    assert e.value.code == hx.binding.CKKS_ERR_INVALID_ARG
+    for bad_value in (1 << (wb - 1), -(1 << (wb - 1))):      # the first magnitudes outside |w| < 2^(wb-1), either sign
+        w_bad = w_int.copy()
+        w_bad[1, 2, 5] = bad_value
+        d_bad = hx.from_host(w_residues(w_bad, ext_moduli, len(ext_moduli) - 1))
+        with pytest.raises(hx.CkksError) as e:
+            hx.he_conv_check_weights(ctx, wl.c_in, wl.c_out, level, d_bad, wb, hx.HE_CONV_DEFERRED_MERGED)
+        assert e.value.code == hx.binding.CKKS_ERR_INVALID_ARG and "weight residues" in str(e.value)
+        offs = conv_tap_offsets(wl.width)
+        dkeys = [hx.ckks_key_load(ctx, hx.from_host(keys[off]), hx.ckks_galois_element(ctx, off)) if off else None for off in offs]
+        args = (ctx, wl.height, wl.width, wl.batch, level, [hx.from_host(c) for c in cts], dkeys, hx.from_host(masks), d_bad, wl.c_out)
+        with pytest.raises(ValueError):
+            hx.he_conv_batched(*args, alignment=hx.HE_CONV_DEFERRED_MERGED, weight_bits=wb, w_int_host=w_bad)
+        with pytest.raises(hx.CkksError):
+            hx.he_conv_batched(*args, alignment=hx.HE_CONV_DEFERRED_MERGED, weight_bits=wb, check_weights=True)
+    w_edge = w_int.copy()
+    w_edge[0, 0, 0], w_edge[0, 0, 1] = (1 << (wb - 1)) - 1, -((1 << (wb - 1)) - 1)                   # the largest admitted magnitudes
+    hx.he_conv_check_weights(ctx, wl.c_in, wl.c_out, level, hx.from_host(w_residues(w_edge, ext_moduli, len(ext_moduli) - 1)), wb,
+                             hx.HE_CONV_DEFERRED_MERGED)
+
+
 def test_he_conv_deferred_needs_extended_operands():
     wl = CONFIGS["cfg1_single_conv"]
     p = wl.params()

@@ -45,7 +45,7 @@ def test_modup_is_c_plus_small_multiple_of_digit_modulus(tiny_params, level):
 
 
 @pytest.mark.parametrize("level", [2, 0])
-def test_moddown_is_floor_division_by_P_up_to_small_error(tiny_params, level):
+def test_moddown_is_rounded_division_by_P_up_to_small_error(tiny_params, level):
     """u == round(V/P) - e (mod Q_level) with |e| <= k/2: |V - P*u| <= (k+1)*P/2, both signs seen."""
     p = tiny_params
     o = Oracle(p)

@@ -142,6 +142,9 @@ CONFIGS: Dict[str, Workload] = {
     "small_rotations": Workload("small_rotations", 13, 7, 3, 3, n_rot=6),
     "small_conv": Workload("small_conv", 13, 5, 2, 3, 8, 8, 64, 3, 2),
     "small_block": Workload("small_block", 12, 8, 3, 3, 8, 8, 32, 2, 2),
+    # 64 input channels (9 * 64 = 576 terms, a whole number of 64-term blocks) and 40 outputs (both 32-channel output tiles live):
+    # the instantiation of the multiply-accumulate that the block-slice benchmark runs, at a size the oracle affords
+    "small_conv_c64": Workload("small_conv_c64", 12, 4, 2, 2, 8, 8, 32, 64, 40),
     # six one-limb digits: more than the fused multi-rotation launches take (the one-launch-per-tap paths)
     "small_conv_d6": Workload("small_conv_d6", 12, 6, 2, 6, 8, 8, 32, 3, 2),
 }
