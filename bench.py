@@ -69,6 +69,7 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--no-kernel-timing", action="store_true", help="skip the per-kernel event pass")
     ap.add_argument("--no-microbench", action="store_true", help="skip the rotation and NTT microbenchmarks")
+    ap.add_argument("--no-schedules", action="store_true", help="skip the other three convolution schedules")
     ap.add_argument("--rotations-only", action="store_true",
                     help="only the rotation microbenchmark (64 hoisted + 64 unhoisted rotations, three times each): for profiling runs")
     ap.add_argument("--ntt-only", action="store_true",
@@ -122,9 +123,36 @@ def cpu_baseline(wl, params, alignment, act_merged):
         (orc.poly_activation_merged if act_merged else orc.poly_activation)(x, level - 1, (3 << 40, -(5 << 40), 7 << 40, -(9 << 40)), key)
     t_act = (time.perf_counter() - t0) / R_ACT
     step = wl.c_in * t_align + wl.c_in * wl.c_out * t_mac + wl.c_out * (t_out + t_act)
-    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    # the threads the oracle's OpenMP loops actually ran on, and the same sample once more on one thread (fewer repetitions)
+    import ctypes
+    gomp = ctypes.CDLL("libgomp.so.1")
+    cores = int(gomp.omp_get_max_threads())
+    gomp.omp_set_num_threads(1)
+    t0 = time.perf_counter()
+    aligned1 = orc.align_deferred(ct, level, wl.width, keys) if deferred else (
+        orc.align_four_keys(ct, level, wl.width, keys) if alignment == "four_keys" else orc.align_direct(ct, level, wl.width, keys))
+    s_align = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    for _ in range(2):
+        acc1 = orc.mac_ext(pts, aligned1, level) if deferred else orc.ptct_mac(pts, aligned1, level)
+    s_mac = (time.perf_counter() - t0) / 2
+    t0 = time.perf_counter()
+    if merged:
+        x1 = np.stack([orc.moddown_rescale(acc1[0], level), orc.moddown_rescale(acc1[1], level)])
+    else:
+        u1 = np.stack([orc.moddown(acc1[0], level), orc.moddown(acc1[1], level)]) if deferred else acc1
+        x1 = orc.rescale(u1, level)
+    s_out = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    (orc.poly_activation_merged if act_merged else orc.poly_activation)(x1, level - 1, (3 << 40, -(5 << 40), 7 << 40, -(9 << 40)), key)
+    s_act = time.perf_counter() - t0
+    gomp.omp_set_num_threads(cores)
+    step1 = wl.c_in * s_align + wl.c_in * wl.c_out * s_mac + wl.c_out * (s_out + s_act)
     return {
         "value": step * 1e3 / wl.batch, "unit": "ms/image", "cores": cores, "kind": "oracle",
+        "single_thread": {"value": step1 * 1e3 / wl.batch, "unit": "ms/image", "cores": 1,
+                          "sample": "one alignment (%.1f s), two 9-tap multiply-accumulates (%.2f s each), one output division (%.1f s), one "
+                                    "activation (%.1f s) on one thread, extrapolated as above" % (s_align, s_mac, s_out, s_act)},
         "sample": ("oracle (%s schedule) timed at full size on %d input channels' alignments (%.2f s each), %d 9-tap "
                    "multiply-accumulates (%.3f s each), %d output channels' %srescale (%.2f s each) and %d degree-7 activations "
                    "(%.2f s each): %.0f s of CPU work, extrapolated to %d alignments, %d 9-tap MACs, %d output channels and activations"
@@ -134,7 +162,7 @@ def cpu_baseline(wl, params, alignment, act_merged):
     }
 
 
-def rotation_microbench(hx, torch, ctx, ct, keys, level, N, ws, result):
+def rotation_microbench(hx, torch, ctx, ct, keys, level, N, ws, result, overlap=True):
     # rotation microbenchmark (24 limbs + 8 special primes, dnum 3): one ciphertext, 64 distinct offsets, 64 keys in
     # 64 separate 96 MiB buffers (their contents are clones of the eight seeded keys: only the addresses matter)
     n_rot_mb = 64
@@ -145,6 +173,7 @@ def rotation_microbench(hx, torch, ctx, ct, keys, level, N, ws, result):
                for i, r in enumerate(mb_offs)]
     mb_outs = [hx.empty(2, level + 1, N) for _ in range(n_rot_mb)]
     for hoisted in (True, False):
+        hx.ckks_ctx_set_overlap(ctx, overlap)
         hx.ckks_rotate_hoisted(ctx, ct, level, mb_offs, mb_keys, hoisted, outs=mb_outs, ws=ws)
         torch.cuda.synchronize()
         reps = 3
@@ -159,6 +188,19 @@ def rotation_microbench(hx, torch, ctx, ct, keys, level, N, ws, result):
         # compulsory HBM traffic per rotation: key 96 MiB + c0 12 MiB + output 24 MiB (+ 24 MiB input when unhoisted)
         mib = (96 + 12 + 24) if hoisted else (96 + 24 + 24)
         result["rotation_%s_effective_GBs" % name] = rate * mib * 2**20 / 1e9
+        result["rotation_%s_frac_of_hbm_peak" % name] = rate * mib * 2**20 / 1e9 / HBM_PEAK_GBS
+    # where a hoisted rotation's time goes: every launch of one more call bracketed by events, all work on one stream
+    hx.ckks_ctx_set_overlap(ctx, False)
+    hx.ckks_prof_begin(ctx, None, max_launches=1 << 14)
+    hx.ckks_rotate_hoisted(ctx, ct, level, mb_offs, mb_keys, True, outs=mb_outs, ws=ws)
+    prof = hx.ckks_prof_end(ctx)
+    prof.pop("dropped")
+    inner = prof.get("key_inner", {"ms": 0.0, "bytes": 0.0})
+    rest = sum(v["ms"] for k, v in prof.items() if k != "key_inner")
+    result["rotation_hoisted_split"] = {
+        "inner_product_us_per_rotation": 1e3 * inner["ms"] / n_rot_mb, "inner_product_GBs": inner["bytes"] / max(inner["ms"], 1e-9) / 1e6,
+        "moddown_and_shared_modup_us_per_rotation": 1e3 * rest / n_rot_mb,
+        "note": "one call of 64 rotations with every launch bracketed, no overlap between batches; the timed rate above lets batches overlap"}
 
 
 def conv_microbench(hx, torch, name, result):
@@ -273,8 +315,7 @@ def main():
 
     if args.rotations_only:
         result = {"workload": "cfg3_rotations (the rotation microbenchmark of the default run)", "single_stream": bool(args.single_stream)}
-        hx.ckks_ctx_set_overlap(ctx, not args.single_stream)
-        rotation_microbench(hx, torch, ctx, ins[0], keys, level, N, ws, result)
+        rotation_microbench(hx, torch, ctx, ins[0], keys, level, N, ws, result, overlap=not args.single_stream)
         print(json.dumps(result))
         return
 
@@ -287,12 +328,19 @@ def main():
         hx.ckks_ctx_set_overlap(ctx, False)
     for _ in range(args.warmup):
         step()
+    # exactly K steps between two synchronisations; every step also sits between two HIP events on the caller's stream (no
+    # host synchronisation inside), which give the per-step median
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    evs[0].record()
+    for i in range(args.steps):
         step()
+        evs[i + 1].record()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    step_ms = sorted(evs[i].elapsed_time(evs[i + 1]) for i in range(args.steps))
+    ms_median = step_ms[len(step_ms) // 2] if len(step_ms) % 2 else 0.5 * (step_ms[len(step_ms) // 2 - 1] + step_ms[len(step_ms) // 2])
     # the same K steps with every launch on the caller's stream: the per-kernel timings below are taken that way, because
     # the duration of a launch that shares the chip with a launch of another batch is not a property of its kernel
     hx.ckks_ctx_set_overlap(ctx, False)
@@ -314,12 +362,13 @@ def main():
         "unit": "ms/image (amortised, conv 64->64 3x3 + degree-7 activation, batch 512)",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
-        "dtype": "u64", "data": "synthetic",
+        "dtype": "u64 residues; fp64-exact butterflies and conversions; int8 MFMA digit products", "data": "synthetic",
         "config": {"workload": wl.name, "log_n": params.log_n, "limbs": params.num_q, "special_primes": params.num_p,
                    "dnum": params.dnum, "c_in": wl.c_in, "c_out": wl.c_out, "image": "%dx%d" % (wl.height, wl.width),
                    "batch": wl.batch, "rotations_per_step": n_rot, "keyswitches_per_step": n_keyswitch,
                    "conv_schedule": args.alignment, "activation": "merged_division" if act_merged else "two_step",
                    "channel_batches_overlap": not args.single_stream, "weight_bits": weight_bits},
+        "ms_per_step_median_events": ms_median, "ms_per_step_min_events": step_ms[0], "ms_per_step_max_events": step_ms[-1],
         "ms_per_step_single_stream": ms_single,
         "kernel_timing": "per-kernel figures and the roofline are measured with all work on one stream (no overlap between channel batches)",
     }
@@ -352,6 +401,8 @@ def main():
         traffic = measured_traffic(dom)
         roof = {"kernel": dom, "launches": v["launches"], "avg_us": 1e6 * secs / v["launches"],
                 "algorithmic_bytes_per_launch": v["bytes"] / v["launches"], "traffic": traffic,
+                "traffic_source": "profiles/pmc_traffic_cfg5_block_slice.txt as committed (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE scaled by a "
+                                  "copy of known size); read from that file, not re-measured by this run",
                 "hbm_GBs": v["bytes"] / secs / 1e9}
         if dom in MFMA_KERNELS:
             per, peak_ops = MFMA_KERNELS[dom]
@@ -372,11 +423,64 @@ def main():
             ach = v["bytes"] / secs / 1e9
             roof.update({"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS})
         result["roofline"] = roof
-        ki = prof.get("key_inner")
-        if ki:
+        if "key_inner" in prof:   # the key inner products of the step, bracketed alone in K more steps (no other event pairs in the stream)
+            hx.ckks_prof_begin(ctx, ["key_inner"], max_launches=1 << 16)
+            for _ in range(args.steps):
+                step()
+            ki = hx.ckks_prof_end(ctx)["key_inner"]
             ach = ki["bytes"] / (ki["ms"] * 1e-3) / 1e9
             result["key_inner_hbm"] = {"achieved_GBs": ach, "frac_of_peak": ach / HBM_PEAK_GBS, "avg_us": 1e3 * ki["ms"] / ki["launches"],
-                                       "traffic": measured_traffic("key_inner")}
+                                       "launches": ki["launches"], "algorithmic_bytes_per_launch": ki["bytes"] / ki["launches"],
+                                       "traffic": measured_traffic("key_inner"), "traffic_source": "profiles/pmc_traffic_cfg5_block_slice.txt as committed"}
+        # a plain device-to-device copy of 2 GiB (the runtime's own copy kernel): what a read-once / write-once stream reaches here
+        cp_src = torch.empty(1 << 28, dtype=torch.int64, device="cuda")
+        cp_dst = torch.empty_like(cp_src)
+        cp_dst.copy_(cp_src)
+        c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        c0.record()
+        for _ in range(10):
+            cp_dst.copy_(cp_src)
+        c1.record()
+        torch.cuda.synchronize()
+        copy_gbs = 10 * 2 * cp_src.numel() * 8 / (c0.elapsed_time(c1) * 1e-3) / 1e9
+        del cp_src, cp_dst
+        result["copy_ceiling"] = {"GB/s": copy_gbs, "frac_of_peak": copy_gbs / HBM_PEAK_GBS, "what": "device-to-device copy of 2 GiB, read + write bytes"}
+        if result["roofline"].get("bound") == "hbm" or "hbm" in result["roofline"]:
+            hb = result["roofline"]["achieved"] if result["roofline"]["bound"] == "hbm" else result["roofline"]["hbm"]["achieved"]
+            result["roofline"]["frac_of_copy_ceiling"] = hb / copy_gbs
+
+    if not args.no_schedules:
+        # the same step under the other readings of where the divisions by P go (three steps each, one warm-up)
+        sched = {args.alignment: ms_per_step}
+        modes = {"direct": hx.HE_CONV_ALIGN_DIRECT, "four_keys": hx.HE_CONV_ALIGN_FOUR_KEYS, "deferred": hx.HE_CONV_DEFERRED_MODDOWN,
+                 "deferred_merged": hx.HE_CONV_DEFERRED_MERGED}
+        hx.ckks_ctx_set_overlap(ctx, not args.single_stream)
+        for name, m in modes.items():
+            if name in sched:
+                continue
+            ext = name.startswith("deferred")
+            qm = (q[:level + 1] + q[params.num_q:]) if ext else q[:level + 1]
+            mk = masks if ext == deferred else hx.from_host(uniform_residues((9, len(qm), N), qm, "masks_" + name))
+            wr = w_res if ext == deferred else hx.from_host(np.stack([np.mod(w_int, qi).astype(np.uint64) for qi in qm], axis=-1))
+            need = hx.he_conv_workspace_bytes(ctx, wl.c_in, wl.c_out, wl.height, wl.width, wl.batch, level, m)
+            wsm = ws if need <= ws.numel() else torch.empty(need, dtype=torch.uint8, device="cuda")
+
+            def other_step():
+                hx.he_conv_batched(ctx, wl.height, wl.width, wl.batch, level, ins, keys, mk, wr, wl.c_out, outs=conv_out, ws=wsm,
+                                   alignment=m, weight_bits=weight_bits)
+                hx.he_poly_act_deg7(ctx, conv_out, level - 1, k_act, rlk, outs=act_out, ws=ws, merged=act_merged)
+            other_step()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(3):
+                other_step()
+            torch.cuda.synchronize()
+            sched[name] = (time.perf_counter() - t0) * 1e3 / 3
+            del mk, wr, wsm
+        result["schedules_ms_per_step"] = sched
+        result["schedules_note"] = ("same activation (%s) in every row; direct = one ModDown per rotation (the literal reading of Eqs. 10-11), four_keys = "
+                                    "the paper's two-stage alignment with four keys, deferred = one ModDown per output channel, deferred_merged = "
+                                    "that ModDown merged with the rescale" % ("merged_division" if act_merged else "two_step"))
 
     if args.calibration_copy:   # a rotation by 0 slots is a plain copy of the ciphertext
         cal = hx.empty(2, level + 1, N)
@@ -390,8 +494,8 @@ def main():
         print(json.dumps(result))
         return
     # ---- the two microbenchmark shapes, reported next to the headline value ------------------------
+    rotation_microbench(hx, torch, ctx, ins[0], keys, level, N, ws, result, overlap=not args.single_stream)
     hx.ckks_ctx_set_overlap(ctx, not args.single_stream)
-    rotation_microbench(hx, torch, ctx, ins[0], keys, level, N, ws, result)
     base_keys = [k for k in keys if k is not None]
     # accumulator merge (the optimised pipeline's block-group transition): 4 intermediate ciphertexts with 8192
     # occupied slots each -> one full ciphertext, at the level the block slice leaves its outputs on
