@@ -163,6 +163,17 @@ int ckks_ptct_mac(const ckks_ctx* ctx, const uint64_t* const* h_d_pts, const uin
 int ckks_rescale(const ckks_ctx* ctx, const uint64_t* d_ct, uint32_t level, uint64_t* d_out,
                  void* d_ws, size_t ws_bytes, void* stream);
 
+/* ckks_rescale for callers that cannot allocate device memory or bring a workspace: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same kernels, same residues; the scratch (the dropped limb in
+ * coefficient form and the forward transforms' first-pass output) is a buffer of CKKS_NOALLOC_SCRATCH_BYTES that is part
+ * of the library's image on every GPU it runs on, so the call needs ckks_workspace_bytes(ctx, CKKS_OP_RESCALE, level, 1)
+ * <= CKKS_NOALLOC_SCRATCH_BYTES ((level + 1) * 16 * N bytes: N = 2^16 up to level 31, N = 2^17 up to level 15) and returns
+ * CKKS_ERR_UNSUPPORTED_PARAMS beyond that.  It calls no allocating routine and does not synchronise.  All calls on one
+ * GPU share the buffer: calls whose work overlaps in time on one GPU (different streams, different contexts) race; on
+ * one stream they are ordered.  The context's device must be the current one. */
+#define CKKS_NOALLOC_SCRATCH_BYTES (32u << 20)
+int ckks_rescale_noalloc(const ckks_ctx* ctx, const uint64_t* d_ct, uint32_t level, uint64_t* d_out, void* stream);
+
 /* Ciphertext product with relinearisation ("Other Layers": polynomial activation):
  * (d0, d1, d2) = (a0 b0, a0 b1 + a1 b0, a1 b1); out = (d0, d1) + KeySwitch(d2, rlk).  No rescale.
  * rlk must be the relinearisation key (galois_elt 0).  d_a may equal d_b. */

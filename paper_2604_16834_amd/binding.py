@@ -42,7 +42,7 @@ HE_RELAYOUT_DEFERRED = 1
 EXPORTS = (
     "ckks_ctx_create", "ckks_ctx_destroy", "ckks_last_error_string", "ckks_workspace_bytes",
     "ckks_ntt_fwd", "ckks_ntt_inv", "ckks_key_load", "ckks_key_free", "ckks_galois_element",
-    "ckks_keyswitch", "ckks_rotate_hoisted", "ckks_ptct_mac", "ckks_rescale", "ckks_ctct_mul_relin",
+    "ckks_keyswitch", "ckks_rotate_hoisted", "ckks_ptct_mac", "ckks_rescale", "ckks_rescale_noalloc", "ckks_ctct_mul_relin",
     "he_conv_workspace_bytes", "he_conv_batched", "he_conv_check_weights", "he_poly_act_deg7", "ckks_f64mod_probe",
     "he_accumulator_workspace_bytes", "he_accumulator_merge", "he_fc_workspace_bytes", "he_fc_batched",
     "he_relayout_workspace_bytes", "he_relayout_two_rotations", "ckks_key_expand_a", "ckks_keyset_stage", "ckks_ctx_set_overlap",
@@ -95,6 +95,7 @@ def _bind(path: str):
     lib.ckks_rotate_hoisted.argtypes = [vp, vp, u32, C.POINTER(C.c_int32), u32, C.POINTER(vp), C.POINTER(vp), i32, vp, sz, vp]
     lib.ckks_ptct_mac.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), u32, u32, vp, i32, vp]
     lib.ckks_rescale.argtypes = [vp, vp, u32, vp, vp, sz, vp]
+    lib.ckks_rescale_noalloc.argtypes = [vp, vp, u32, vp, vp]
     lib.ckks_ctct_mul_relin.argtypes = [vp, vp, vp, u32, vp, vp, vp, sz, vp]
     lib.he_conv_workspace_bytes.argtypes = [vp, C.POINTER(_ConvDesc)]
     lib.he_conv_workspace_bytes.restype = sz
@@ -310,6 +311,14 @@ def ckks_rescale(ctx: Context, ct: torch.Tensor, level: int, out: Optional[torch
         out = empty(2, max(level, 1), ctx.N)
     ws = _ws(ctx, ws, ckks_workspace_bytes(ctx, CKKS_OP_RESCALE, level))
     ctx._check(_lib.ckks_rescale(ctx.handle, _ptr(ct), level, _ptr(out), _ptr(ws), ws.numel() * ws.element_size(), _stream(stream)))
+    return out
+
+
+def ckks_rescale_noalloc(ctx: Context, ct: torch.Tensor, level: int, out: torch.Tensor, stream=None) -> torch.Tensor:
+    """ckks_rescale on the library's built-in scratch buffer: no workspace, no allocation (the caller brings `out`)."""
+    if ct.numel() != 2 * (level + 1) * ctx.N or out.numel() != 2 * max(level, 1) * ctx.N:
+        raise ValueError("ct must be [2][level+1][N] and out [2][level][N]")
+    ctx._check(_lib.ckks_rescale_noalloc(ctx.handle, _ptr(ct), level, _ptr(out), _stream(stream)))
     return out
 
 

@@ -11,7 +11,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 OBJ = os.path.join(_HERE, "_build")
 OUT = os.path.join(_HERE, "libckks_mi355x.so")
-SOURCES = ["ntt.hip", "keyswitch.hip", "pointwise.hip", "wsum_mfma.hip", "keystage.hip", "selftest.hip", "context.cpp", "api.cpp"]
+SOURCES = ["ntt.hip", "keyswitch.hip", "pointwise.hip", "wsum_mfma.hip", "keystage.hip", "noalloc.hip", "selftest.hip", "context.cpp", "api.cpp"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # keep the compiler from forming packed-fp32 instructions (no float math on this path anyway)

@@ -117,6 +117,7 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
 
     ckks_ctx* c = new (std::nothrow) ckks_ctx;
     if (!c) return fail(CKKS_ERR_INVALID_ARG, "out of host memory");
+    if (hipGetDevice(&c->device) != hipSuccess) { delete c; return fail(CKKS_ERR_HIP, "no current HIP device"); }
     c->log_n = p->log_n; c->N = N; c->num_q = p->num_q; c->num_p = p->num_p; c->dnum = p->dnum; c->alpha = alpha; c->M = M;
     c->log_lo = p->log_n < CKKS_TILE_LOG ? p->log_n : CKKS_TILE_LOG;
     c->log_hi = p->log_n - c->log_lo;
@@ -384,6 +385,12 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
         g_create_error = std::string("HIP error while building tables: ") + hipGetErrorString(e);
+        ckks_ctx_destroy(c);
+        return CKKS_ERR_HIP;
+    }
+    // the built-in scratch of the call that takes no workspace: its address on this device, looked up once, here
+    if ((e = noalloc_scratch_current_device(nullptr, nullptr)) != hipSuccess) {
+        g_create_error = std::string("HIP error while looking up the built-in scratch buffer: ") + hipGetErrorString(e);
         ckks_ctx_destroy(c);
         return CKKS_ERR_HIP;
     }

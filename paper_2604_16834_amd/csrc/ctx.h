@@ -163,6 +163,8 @@ struct ckks_ctx {
     bool overlap = true;  // ckks_ctx_set_overlap: off = everything on the caller's stream
     hipStream_t side_stream() const { return overlap ? side : nullptr; }
 
+    int device = 0;  // the HIP device the tables live on (the one that was current at creation)
+
     mutable std::string err;
     mutable ProfState* prof = nullptr;  // non-null between ckks_prof_begin and ckks_prof_end
 
@@ -205,6 +207,9 @@ struct ProfScope {
         if (pair >= 0) (void)hipEventRecord(c->prof->events[2 * pair + 1], st);
     }
 };
+
+// noalloc.hip: the device address of the library's built-in scratch array on the current device (looked up on first use)
+hipError_t noalloc_scratch_current_device(int* device, void** ptr);
 
 // ---- kernel launchers (each enqueues on `st` and returns the launch status) -------------------
 // ntt.hip: batch x pl.n limb-polys; item b reads src + b*src_bstride*N (or src_ptrs[b] when given: host
