@@ -74,6 +74,10 @@ def parse_args():
                     help="only the rotation microbenchmark (64 hoisted + 64 unhoisted rotations, three times each): for profiling runs")
     ap.add_argument("--ntt-only", action="store_true",
                     help="only the NTT microbenchmark (64 x 30 limb transforms at N = 2^16, forward and inverse, six times): for profiling runs")
+    ap.add_argument("--fc-only", action="store_true", help="only the fully connected layer at the classifier's shape, ten times: for profiling runs")
+    ap.add_argument("--downsample-only", action="store_true", help="only the down-sampling compaction (both schedules, three times each): for profiling runs")
+    ap.add_argument("--prime-bits", type=int, default=50,
+                    help="size of the primes for --ntt-only / --rotations-only (56: the 64-bit integer kernels instead of the double-precision ones)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run the library's plain copy kernel on one ciphertext (24 MiB in, 24 MiB out): the known-size "
                          "dispatch that hardware-counter runs are scaled by")
@@ -240,10 +244,11 @@ def conv_microbench(hx, torch, name, result):
                               "special_primes": params.num_p, "schedule": "deferred_merged"}
 
 
-def ntt_microbench(hx, torch, result):
-    from workloads import CONFIGS, uniform_residues
+def ntt_microbench(hx, torch, result, bits=50):
+    from workloads import CONFIGS, make_params, uniform_residues
     # NTT microbenchmark: 64 polynomials x 30 limbs at N = 2^16, forward then inverse
-    p2 = CONFIGS["cfg2_ntt"].params()
+    w2 = CONFIGS["cfg2_ntt"]
+    p2 = make_params(w2.log_n, w2.num_q, w2.num_p, w2.dnum, bits=bits)
     ctx2 = hx.Context(p2)
     polys = hx.from_host(uniform_residues((64, p2.num_q, p2.n), p2.moduli, "cfg2"))
     idx2 = list(range(p2.num_q))
@@ -261,6 +266,90 @@ def ntt_microbench(hx, torch, result):
     result["ntt_butterflies_per_s"] = result["ntt_limbs_per_s"] * (p2.n // 2) * p2.log_n
 
 
+def fc_bench(hx, torch, ctx, params, ins, masks, base_keys, level, N, result):
+    # batched fully connected layer at the classifier's shape: 64 -> 10 on 512 images (all N/2 slots), level 3,
+    # base = ceil(sqrt(512)); every one of its 59 rotations has a key tensor of its own (random residues)
+    fc_in, fc_out, fc_batch, fc_level, fc_base = 64, 10, 512, 3, 23
+    fc_delta = fc_in - fc_out
+    fc_offs = [[1 << t for t in range(6)], [-i for i in range(fc_out)], [l * fc_delta for l in range(fc_base)],
+               [h * fc_base * fc_delta for h in range(-(-fc_batch // fc_base))]]
+    fc_keys = [[None if r % (N // 2) == 0 else
+                hx.ckks_key_load(ctx, base_keys[(7 * i + j) % len(base_keys)].tensor.clone(), hx.ckks_galois_element(ctx, r))
+                for j, r in enumerate(offs)] for i, offs in enumerate(fc_offs)]
+    fc_ct = ins[0][:, :fc_level + 1].contiguous()
+    fc_w = torch.stack([masks[i % 9, :fc_level + 1] for i in range(fc_out)]).contiguous()
+    fc_mm = masks[0, :fc_level].contiguous()
+    fc_pm = torch.stack([masks[i % 9, :fc_level - 1] for i in range(fc_batch)]).contiguous()
+    fc_b = masks[1, :fc_level - 2].contiguous()
+    fc_o = hx.empty(2, fc_level - 2, N)
+    fc_ws = hx.empty(hx.he_fc_workspace_bytes(ctx, fc_in, fc_out, fc_batch, fc_level, fc_base) // 8)
+    run_fc = lambda: hx.he_fc_batched(ctx, fc_ct, fc_level, fc_in, fc_out, fc_batch, fc_base, fc_w, fc_mm, fc_pm, fc_b,
+                                      *fc_keys, out=fc_o, ws=fc_ws)
+    run_fc()
+    torch.cuda.synchronize()
+    reps = 10
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        run_fc()
+    torch.cuda.synchronize()
+    fc_dt = (time.perf_counter() - t0) / reps
+    result["fc_layer_ms"] = fc_dt * 1e3
+    result["fc_layer_ms_per_image"] = fc_dt * 1e3 / fc_batch
+    result["fc_layer_shape"] = {"d_in": fc_in, "d_out": fc_out, "batch": fc_batch, "level": fc_level, "base": fc_base,
+                                "key_switches": sum(k is not None for ks in fc_keys for k in ks) + (fc_out - 1) * 6}
+    del fc_keys, fc_ws
+
+
+def downsample_bench(hx, torch, ctx, params, ins, masks, base_keys, level, N, result):
+    # down-sampling compaction at the stage-2 -> stage-3 transition: 64 channel ciphertexts of 128 images of 16x16 -> 8x8, at
+    # the level the slice ends on.  Two re-layouts (inside the images, then whole images), in two configurations:
+    #   direct    8 + 8 and 12 + 11 offsets, every rotation divided by P on its own (35 keys)
+    #   deferred  16 + 4 and 32 + 4 offsets, divisions after the sums: first rotations are inner products only (52 keys)
+    ds_level, ds_n, kp = level - 5, 64, params.num_p
+    ds_in = [hx.empty(2, ds_level + 1, N).copy_(ins[i % len(ins)][:, :ds_level + 1]) for i in range(ds_n)]
+    ds_plans = {
+        "direct": (hx.HE_RELAYOUT_DIRECT, [([x for x in range(8)], [y * 24 for y in range(8)], 64),
+                                            ([l * 192 for l in range(12)], [h * 12 * 192 for h in range(11)], 128)]),
+        "deferred": (hx.HE_RELAYOUT_DEFERRED, [([y * 24 + x for y in range(2) for x in range(8)], [h * 48 for h in range(4)], 64),
+                                                ([l * 192 for l in range(32)], [h * 32 * 192 for h in range(4)], 128)]),
+    }
+    for name, (sched, stages) in ds_plans.items():
+        ds_ws = hx.empty(max(hx.he_relayout_workspace_bytes(ctx, ds_level - k, ds_n, len(lo), len(hi), sched)
+                             for k, (lo, hi, _) in enumerate(stages)) // 8)
+        ds_args = []
+        for k, (lo, hi, n_pairs) in enumerate(stages):
+            lv = ds_level - k
+            mk = lambda offs, salt: [None if r % (N // 2) == 0 else
+                                     hx.ckks_key_load(ctx, base_keys[(salt + j) % len(base_keys)].tensor.clone(), hx.ckks_galois_element(ctx, r))
+                                     for j, r in enumerate(offs)]
+            if sched == hx.HE_RELAYOUT_DEFERRED:   # masks on the extended basis: the live q-limbs, then the special primes
+                pool = [torch.cat([masks[i, :lv + 1], masks[i, level + 1:level + 1 + kp]]).contiguous() for i in range(9)]
+            else:
+                pool = [masks[i, :lv + 1].contiguous() for i in range(9)]
+            ms = [[(pool[(h * len(lo) + l) % 9] if h * len(lo) + l < n_pairs else None) for l in range(len(lo))] for h in range(len(hi))]
+            ds_args.append((lv, lo, mk(lo, 3 * k), hi, mk(hi, 3 * k + 5), ms, [hx.empty(2, lv, N) for _ in range(ds_n)]))
+
+        def run_ds():
+            cur = ds_in
+            for lv, lo, lk, hi, hk, ms, outs in ds_args:
+                cur = hx.he_relayout_two_rotations(ctx, cur, lv, lo, lk, hi, hk, ms, schedule=sched, outs=outs, ws=ds_ws)
+        run_ds()
+        torch.cuda.synchronize()
+        reps = 3
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            run_ds()
+        torch.cuda.synchronize()
+        ds_dt = (time.perf_counter() - t0) / reps
+        result["downsample_%s" % name] = {
+            "ms": ds_dt * 1e3, "ms_per_image": ds_dt * 1e3 / 128, "offsets": [[len(lo), len(hi)] for lo, hi, _ in stages],
+            "keys": sum(1 for lo, hi, _ in stages for r in lo + hi if r % (N // 2)),
+            "inner_products": ds_n * sum(1 for lo, hi, _ in stages for r in lo + hi if r % (N // 2))}
+        del ds_args, ds_ws
+    result["downsample_shape"] = {"channels": ds_n, "from": "16x16", "to": "8x8", "batch": 128, "level": ds_level}
+    del ds_in
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -274,12 +363,15 @@ def main():
     from workloads import CONFIGS, conv_tap_offsets, uniform_residues
 
     if args.ntt_only:
-        result = {"workload": "cfg2_ntt (the NTT microbenchmark of the default run)"}
-        ntt_microbench(hx, torch, result)
+        result = {"workload": "cfg2_ntt (the NTT microbenchmark of the default run)", "prime_bits": args.prime_bits}
+        ntt_microbench(hx, torch, result, bits=args.prime_bits)
         print(json.dumps(result))
         return
     wl = CONFIGS[args.workload]
     params = wl.params()
+    if args.prime_bits != 50:   # other prime sizes (the integer kernels above 2^50) for the microbenchmark-only runs
+        from workloads import make_params
+        params = make_params(wl.log_n, wl.num_q, wl.num_p, wl.dnum, bits=args.prime_bits)
     ctx = hx.Context(params)
     N, level, q = params.n, params.num_q - 1, params.moduli
     M = params.num_q + params.num_p
@@ -313,8 +405,16 @@ def main():
     torch.cuda.synchronize()
     print("[bench] setup %.1f s, workspace %.2f GiB" % (time.perf_counter() - t_setup, ws_bytes / 2**30), file=sys.stderr, flush=True)
 
+    if args.fc_only or args.downsample_only:
+        result = {"workload": "fc layer 64 -> 10 x 512 images at level 3" if args.fc_only else "down-sampling compaction 64 channels x 128 images 16x16 -> 8x8"}
+        base_keys = [k for k in keys if k is not None]
+        hx.ckks_ctx_set_overlap(ctx, not args.single_stream)
+        (fc_bench if args.fc_only else downsample_bench)(hx, torch, ctx, params, ins, masks, base_keys, level, N, result)
+        print(json.dumps(result))
+        return
     if args.rotations_only:
-        result = {"workload": "cfg3_rotations (the rotation microbenchmark of the default run)", "single_stream": bool(args.single_stream)}
+        result = {"workload": "cfg3_rotations (the rotation microbenchmark of the default run)", "single_stream": bool(args.single_stream),
+                  "prime_bits": args.prime_bits}
         rotation_microbench(hx, torch, ctx, ins[0], keys, level, N, ws, result, overlap=not args.single_stream)
         print(json.dumps(result))
         return
@@ -513,84 +613,8 @@ def main():
     torch.cuda.synchronize()
     result["accumulator_merges_per_s"] = reps / (time.perf_counter() - t0)
     result["accumulator_merge_shape"] = {"g": acc_g, "sts": acc_sts, "level": acc_level}
-    # batched fully connected layer at the classifier's shape: 64 -> 10 on 512 images (all N/2 slots), level 3,
-    # base = ceil(sqrt(512)); every one of its 59 rotations has a key tensor of its own (random residues)
-    fc_in, fc_out, fc_batch, fc_level, fc_base = 64, 10, 512, 3, 23
-    fc_delta = fc_in - fc_out
-    fc_offs = [[1 << t for t in range(6)], [-i for i in range(fc_out)], [l * fc_delta for l in range(fc_base)],
-               [h * fc_base * fc_delta for h in range(-(-fc_batch // fc_base))]]
-    fc_keys = [[None if r % (N // 2) == 0 else
-                hx.ckks_key_load(ctx, base_keys[(7 * i + j) % len(base_keys)].tensor.clone(), hx.ckks_galois_element(ctx, r))
-                for j, r in enumerate(offs)] for i, offs in enumerate(fc_offs)]
-    fc_ct = ins[0][:, :fc_level + 1].contiguous()
-    fc_w = torch.stack([masks[i % 9, :fc_level + 1] for i in range(fc_out)]).contiguous()
-    fc_mm = masks[0, :fc_level].contiguous()
-    fc_pm = torch.stack([masks[i % 9, :fc_level - 1] for i in range(fc_batch)]).contiguous()
-    fc_b = masks[1, :fc_level - 2].contiguous()
-    fc_o = hx.empty(2, fc_level - 2, N)
-    fc_ws = hx.empty(hx.he_fc_workspace_bytes(ctx, fc_in, fc_out, fc_batch, fc_level, fc_base) // 8)
-    run_fc = lambda: hx.he_fc_batched(ctx, fc_ct, fc_level, fc_in, fc_out, fc_batch, fc_base, fc_w, fc_mm, fc_pm, fc_b,
-                                      *fc_keys, out=fc_o, ws=fc_ws)
-    run_fc()
-    torch.cuda.synchronize()
-    reps = 10
-    t0 = time.perf_counter()
-    for _ in range(reps):
-        run_fc()
-    torch.cuda.synchronize()
-    fc_dt = (time.perf_counter() - t0) / reps
-    result["fc_layer_ms"] = fc_dt * 1e3
-    result["fc_layer_ms_per_image"] = fc_dt * 1e3 / fc_batch
-    result["fc_layer_shape"] = {"d_in": fc_in, "d_out": fc_out, "batch": fc_batch, "level": fc_level, "base": fc_base,
-                                "key_switches": sum(k is not None for ks in fc_keys for k in ks) + (fc_out - 1) * 6}
-    del fc_keys, fc_ws
-    # down-sampling compaction at the stage-2 -> stage-3 transition: 64 channel ciphertexts of 128 images of 16x16 -> 8x8, at
-    # the level the slice ends on.  Two re-layouts (inside the images, then whole images), in two configurations:
-    #   direct    8 + 8 and 12 + 11 offsets, every rotation divided by P on its own (35 keys)
-    #   deferred  16 + 4 and 32 + 4 offsets, divisions after the sums: first rotations are inner products only (52 keys)
-    ds_level, ds_n, kp = level - 5, 64, params.num_p
-    ds_in = [hx.empty(2, ds_level + 1, N).copy_(ins[i % len(ins)][:, :ds_level + 1]) for i in range(ds_n)]
-    ds_plans = {
-        "direct": (hx.HE_RELAYOUT_DIRECT, [([x for x in range(8)], [y * 24 for y in range(8)], 64),
-                                            ([l * 192 for l in range(12)], [h * 12 * 192 for h in range(11)], 128)]),
-        "deferred": (hx.HE_RELAYOUT_DEFERRED, [([y * 24 + x for y in range(2) for x in range(8)], [h * 48 for h in range(4)], 64),
-                                                ([l * 192 for l in range(32)], [h * 32 * 192 for h in range(4)], 128)]),
-    }
-    for name, (sched, stages) in ds_plans.items():
-        ds_ws = hx.empty(max(hx.he_relayout_workspace_bytes(ctx, ds_level - k, ds_n, len(lo), len(hi), sched)
-                             for k, (lo, hi, _) in enumerate(stages)) // 8)
-        ds_args = []
-        for k, (lo, hi, n_pairs) in enumerate(stages):
-            lv = ds_level - k
-            mk = lambda offs, salt: [None if r % (N // 2) == 0 else
-                                     hx.ckks_key_load(ctx, base_keys[(salt + j) % len(base_keys)].tensor.clone(), hx.ckks_galois_element(ctx, r))
-                                     for j, r in enumerate(offs)]
-            if sched == hx.HE_RELAYOUT_DEFERRED:   # masks on the extended basis: the live q-limbs, then the special primes
-                pool = [torch.cat([masks[i, :lv + 1], masks[i, level + 1:level + 1 + kp]]).contiguous() for i in range(9)]
-            else:
-                pool = [masks[i, :lv + 1].contiguous() for i in range(9)]
-            ms = [[(pool[(h * len(lo) + l) % 9] if h * len(lo) + l < n_pairs else None) for l in range(len(lo))] for h in range(len(hi))]
-            ds_args.append((lv, lo, mk(lo, 3 * k), hi, mk(hi, 3 * k + 5), ms, [hx.empty(2, lv, N) for _ in range(ds_n)]))
-
-        def run_ds():
-            cur = ds_in
-            for lv, lo, lk, hi, hk, ms, outs in ds_args:
-                cur = hx.he_relayout_two_rotations(ctx, cur, lv, lo, lk, hi, hk, ms, schedule=sched, outs=outs, ws=ds_ws)
-        run_ds()
-        torch.cuda.synchronize()
-        reps = 3
-        t0 = time.perf_counter()
-        for _ in range(reps):
-            run_ds()
-        torch.cuda.synchronize()
-        ds_dt = (time.perf_counter() - t0) / reps
-        result["downsample_%s" % name] = {
-            "ms": ds_dt * 1e3, "ms_per_image": ds_dt * 1e3 / 128, "offsets": [[len(lo), len(hi)] for lo, hi, _ in stages],
-            "keys": sum(1 for lo, hi, _ in stages for r in lo + hi if r % (N // 2)),
-            "inner_products": ds_n * sum(1 for lo, hi, _ in stages for r in lo + hi if r % (N // 2))}
-        del ds_args, ds_ws
-    result["downsample_shape"] = {"channels": ds_n, "from": "16x16", "to": "8x8", "batch": 128, "level": ds_level}
-    del ds_in
+    fc_bench(hx, torch, ctx, params, ins, masks, base_keys, level, N, result)
+    downsample_bench(hx, torch, ctx, params, ins, masks, base_keys, level, N, result)
     # key staging: the block group's 9 keys (8 rotations + relinearisation) as b halves in pinned host memory (48 MiB
     # each) + seeds, copied and expanded on a side stream, alone and while the block slice runs on the main stream
     n_stage = 9
