@@ -115,6 +115,11 @@ void ckks_key_free(ckks_key* key);
  * seed: a[j][t][x] = the top bitlength(q_t) bits of the first of the outputs 64e, 64e+1, ... (e = (j*M + t)*N + x,
  * M = num_q+num_p) of the SplitMix64 sequence started at the seed that is below q_t (the 64th output reduced mod
  * q_t if none is).  Half the bytes cross the host link.
+ * SplitMix64 is a stand-in here: it is not a cryptographic generator and its state is 64 bits, while the security argument
+ * for seeded public halves needs an expansion by a pseudo-random function or extendable-output function keyed with at
+ * least 128 bits (the paper runs at a 128-bit setting: Experiments, "HE Security Parameters").  The benchmark measures the
+ * data movement and the expansion's cost; a deployment replaces the one device function that produces output number
+ * `index` of the stream (and the seed type) and keeps everything else.
  * ckks_key_expand_a writes the a halves of d_key (uint64[dnum][2][M][N]); the b halves are left as they are.
  * ckks_keyset_stage enqueues, for each of n_keys keys, the copy of h_b[i] (pinned host memory for the copy to be
  * asynchronous) into the b halves of h_d_keys[i] and the expansion of h_a_seeds[i], all on `stream` (normally a

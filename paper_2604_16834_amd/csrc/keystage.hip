@@ -8,9 +8,11 @@
 
 namespace {
 
-// Output number `index` of the SplitMix64 sequence started at `seed` (Steele, Lea, Flood 2014): the state
-// advances by a constant, so every output can be computed on its own.
-__device__ __forceinline__ u64 splitmix64_at(u64 seed, u64 index) {
+// Output number `index` of the stream that a seed expands to.  This is the one function to replace for deployment: the
+// stream here is the SplitMix64 sequence started at `seed` (Steele, Lea, Flood 2014; the state advances by a constant, so
+// every output can be computed on its own), which is a benchmarking stand-in, not a cryptographic expansion: seeded
+// public key halves need a PRF / XOF keyed with at least 128 bits.
+__device__ __forceinline__ u64 seed_stream_at(u64 seed, u64 index) {
     u64 z = seed + (index + 1) * 0x9E3779B97F4A7C15ull;
     z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
     z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
@@ -30,7 +32,7 @@ __global__ __launch_bounds__(256) void key_expand_a_kernel(u64* __restrict__ key
     u64 z = 0, v = 0;
     bool found = false;
     for (u32 attempt = 0; attempt < 64 && !found; attempt++) {
-        z = splitmix64_at(seed, e * 64 + attempt);
+        z = seed_stream_at(seed, e * 64 + attempt);
         v = z >> shift;
         found = v < q;
     }
