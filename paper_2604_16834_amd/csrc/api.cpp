@@ -535,8 +535,9 @@ int conv_deferred(const ckks_ctx* c, const he_conv_desc* d, const u32* gs, const
 // n <= CT_BATCH different ciphertexts srcs[b] ([2][level+1][N]) rotated, outs[b] = Rot(srcs[b]) with keys[b] / gal[b]
 // ([2][level+1][N], no overlap).  Neighbouring items with the same key go through one inner-product launch (the key
 // streams once for all of them).
+// accs (optional): outs[b] = Rot(srcs[b]) + accs[b], the sum formed by the division's last step.
 int run_rotate_batch(const ckks_ctx* c, u32 level, u32 n, const u64* const* srcs, const ckks_key* const* keys, const u32* gal,
-                     u64* const* outs, const KsWs& ws, hipStream_t st) {
+                     u64* const* outs, const KsWs& ws, hipStream_t st, const u64* const* accs = nullptr) {
     const size_t N = c->N, L1 = level + 1;
     const u64* c1s[CT_BATCH];
     FinalItem items[CT_BATCH];
@@ -553,7 +554,7 @@ int run_rotate_batch(const ckks_ctx* c, u32 level, u32 n, const u64* const* srcs
                                            ws.v_b, b1 - b0, st));
         b0 = b1;
     }
-    for (u32 b = 0; b < n; b++) items[b] = FinalItem{srcs[b], nullptr, nullptr, outs[b], gal[b], 0};
+    for (u32 b = 0; b < n; b++) items[b] = FinalItem{srcs[b], nullptr, nullptr, outs[b], gal[b], 0, accs ? accs[b] : nullptr};
     return run_moddown(c, level, ws, n, items, st);
 }
 
@@ -1492,19 +1493,23 @@ int he_fc_batched(const ckks_ctx* c, const he_fc_desc* d, const uint64_t* d_in, 
             orot[b] = Srot + b * ct1;
         }
         if ((rc = run_rescale(c, level, pp, (size_t)(level + 1) * N, os, n, ar.rest(), st))) return rc;
+        // T <- T + Rot(T, 2^s): the sum rides on the rotation's last kernel, the running sums alternate between two buffers
+        const u64* cur[CT_BATCH];
+        u64* nxt[CT_BATCH];
+        for (u32 b = 0; b < n; b++) cur[b] = ps[b];
         for (u32 s = 0; s < n_sum; s++) {
             const ckks_key* ks[CT_BATCH];
             u32 gs[CT_BATCH];
             for (u32 b = 0; b < n; b++) {
                 ks[b] = sum_keys[s];
                 gs[b] = g_sum[s];
+                nxt[b] = (s & 1) ? os[b] : orot[b];
             }
-            if ((rc = run_rotate_batch(c, l1, n, ps, ks, gs, orot, ws, st))) return rc;
-            for (u32 b = 0; b < n; b++) {
-                const u64* two[2] = {ps[b], orot[b]};
-                HIP_TRY(launch_ct_sum(c, l1, ptr_list(two, 2), 2, os[b], st));
-            }
+            if ((rc = run_rotate_batch(c, l1, n, cur, ks, gs, nxt, ws, st, cur))) return rc;
+            for (u32 b = 0; b < n; b++) cur[b] = nxt[b];
         }
+        if (n_sum & 1)  // an odd number of steps ends in the second buffer
+            for (u32 b = 0; b < n; b++) HIP_TRY(launch_copy(orot[b], os[b], ct1, st));
     }
     // 2. merge over the outputs: element (j, i) to slot j*d_in + i
     {

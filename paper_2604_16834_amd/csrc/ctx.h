@@ -80,6 +80,7 @@ struct FinalItem {
     u64* out;
     u32 g;
     u32 pad;
+    const u64* acc;  // optional: a ciphertext shaped like `out`, added to it as it is (no gather, after the mask): out = ... + acc
 };
 // Where the inner-product kernels find the extended digits of batch item b: digit j, position e of the extended basis is
 // row (j*E + e) of digits + b*bstride, except for the digit's OWN limbs (e <= level, e / alpha == j), which ModUp does not

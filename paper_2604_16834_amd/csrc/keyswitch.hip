@@ -734,6 +734,7 @@ __global__ __launch_bounds__(KS_THREADS) void moddown_final_kernel(const u64* __
         r = add_mod(r, add[(size_t)i * N + xs], m.q);
     }
     if (it.mask) r = mulmod_barrett(r, it.mask[(size_t)i * N + x], m);
+    if (it.acc) r = add_mod(r, it.acc[((size_t)comp * n_out + i) * N + x], m.q);
     it.out[((size_t)comp * n_out + i) * N + x] = r;
 }
 
@@ -745,9 +746,9 @@ hipError_t launch_moddown_final(const ckks_ctx* c, u32 level, bool merged, const
     for (u32 r = 0; r < KS_MAX_BATCH; r++) {
         if (r < n) {
             B.it[r] = items[r];
-            extra += (items[r].add0 ? 1.0 : 0.0) + (items[r].add1 ? 1.0 : 0.0) + (items[r].mask ? 1.0 : 0.0);
+            extra += (items[r].add0 ? 1.0 : 0.0) + (items[r].add1 ? 1.0 : 0.0) + (items[r].mask ? 1.0 : 0.0) + (items[r].acc ? 2.0 : 0.0);
         } else {
-            B.it[r] = FinalItem{nullptr, nullptr, nullptr, nullptr, 1, 0};
+            B.it[r] = FinalItem{nullptr, nullptr, nullptr, nullptr, 1, 0, nullptr};
         }
     }
     const u32 n_out = merged ? level : level + 1;

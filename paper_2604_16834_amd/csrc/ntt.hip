@@ -384,6 +384,7 @@ __device__ __forceinline__ void fwd_lo_body(const NttArgs& args, const PolyList&
                         r = A::reduce(r + A::from_u64(add[((size_t)i << args.log_n) + xs]), P.mc);
                     }
                     if (fi.mask) r = A::mulmod_any(r, A::from_u64(fi.mask[((size_t)i << args.log_n) + off + p]), q, P.mc.qinv);
+                    if (fi.acc) r = A::reduce(r + A::from_u64(fi.acc[(((size_t)comp * ep.n_out + i) << args.log_n) + off + p]), P.mc);
                     orow[p] = A::canonical(r, P.mc);
                 }
             } else {
@@ -400,6 +401,7 @@ __device__ __forceinline__ void fwd_lo_body(const NttArgs& args, const PolyList&
                         r = add_mod(r, add[((size_t)i << args.log_n) + xs], mi.q);
                     }
                     if (fi.mask) r = mulmod_barrett(r, fi.mask[((size_t)i << args.log_n) + off + p], mi);
+                    if (fi.acc) r = add_mod(r, fi.acc[(((size_t)comp * ep.n_out + i) << args.log_n) + off + p], mi.q);
                     orow[p] = r;
                 }
             }
