@@ -173,18 +173,23 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
         }
     }
 
-    // powers of 256 modulo every modulus, in 25-bit halves: the matrix-core multiply-accumulate folds its 13 digit
-    // diagonals with them
-    std::vector<u32> pow256;
+    // powers of 256 modulo every modulus, in parts of 17, 17 and 16 bits: the matrix-core multiply-accumulate folds its 13
+    // digit diagonals with them in exact double-precision sums (f64m_fold_diagonals)
+    std::vector<double> pow256;
     if (c->small_q) {
-        pow256.resize((size_t)M * 26);
+        pow256.assign((size_t)M * POW256_ROW, 0.0);
         for (u32 t = 0; t < M; t++) {
+            double* row = &pow256[(size_t)t * POW256_ROW];
             u64 v = 1 % c->mod[t];
             for (u32 s = 0; s < 13; s++) {
-                pow256[(size_t)t * 26 + 2 * s] = (u32)(v & 0x1ffffffu);
-                pow256[(size_t)t * 26 + 2 * s + 1] = (u32)(v >> 25);
+                row[3 * s] = (double)(v & 0x1ffffu);
+                row[3 * s + 1] = (double)((v >> 17) & 0x1ffffu);
+                row[3 * s + 2] = (double)(v >> 34);
                 v = h_mulmod(v, 256, c->mod[t]);
             }
+            const u64 w17 = 131072 % c->mod[t];
+            row[39] = (double)w17;
+            row[40] = (double)w17 / (double)c->mod[t];
         }
     }
     // ModUp tables, one per (level, digit): the digit modulus is the product of the digit's LIVE limbs

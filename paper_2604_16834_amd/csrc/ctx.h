@@ -29,6 +29,8 @@ struct __attribute__((aligned(16))) TwPair {
 
 // the same for the double-precision butterflies: TwF (f64mod.h), the twiddle as a double and twiddle / q rounded to nearest
 // per-modulus constants of the double-precision butterflies
+#define POW256_ROW 42  // 13 x 3 parts, 2^17 mod q, (2^17 mod q) / q, one word of padding
+
 struct ModConstF {
     double q, qinv;        // the modulus and 1/q rounded to nearest
     double ninv, ninv_q;   // N^-1 mod q and (N^-1 mod q) / q
@@ -134,7 +136,7 @@ struct ckks_ctx {
     TwF* d_twf = nullptr;             // [M][N]  psi^bitrev(i) and psi^bitrev(i) / q as doubles
     TwF* d_itwf = nullptr;
     ModConstF* d_mcf = nullptr;       // [M]
-    u32* d_pow256 = nullptr;          // [M][13][2]: 2^(8s) mod q split into its low 25 bits and the rest (moduli below 2^50 only)
+    double* d_pow256 = nullptr;       // [M][POW256_ROW]: 2^(8s) mod q, s < 13, in parts of 17, 17 and 16 bits, then 2^17 mod q and its quotient by q (moduli below 2^50 only)
     u64* d_modup = nullptr;           // per level, per digit: see modup_digit_stride()
     u64* d_moddown = nullptr;         // phat_inv[k_pad], phat_inv_sh[k_pad], phat_q[num_q][k_pad], pinv[num_q], pinv_sh[num_q], negp[num_q]
     u64* d_moddown_rs = nullptr;      // per level l >= 1, the same layout (k_pad -> k2_pad) for the dropped set {q_l, p_0..p_{k-1}}:

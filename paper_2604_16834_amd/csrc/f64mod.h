@@ -95,3 +95,25 @@ F64M_FN double f64m_dot(const double* y, const TwF* cw, double q, double qinv) {
     }
     return f64m_reduce(s, q, qinv);
 }
+
+// sum_s D[s] * c[s]  mod q  as a reduced double, for 32-bit signed D[s] and ND <= 13 constants c[s] < q given in three
+// parts, c[s] = c0[s] + 2^17 c1[s] + 2^34 c2[s] with c0, c1 < 2^17 and c2 < 2^16 (the digit diagonals of a sum of 8-bit
+// digit products and the powers of 256 they stand for).  Each of the three sums of ND products is below
+// 13 * 2^31 * 2^17 < 2^52 in magnitude, so it is exact; the sums are joined by Horner's rule with the multiplier
+// w17 = 2^17 mod q (w17q = w17 / q rounded to nearest), every multiplicand reduced first so that any modulus from 3 up works.
+// cparts: [ND][3] doubles.
+template <int ND>
+F64M_FN double f64m_fold_diagonals(const int* D, const double* cparts, double w17, double w17q, double q, double qinv) {
+    static_assert(ND <= 13, "the three partial sums must stay below 2^52");
+    double s0 = 0.0, s1 = 0.0, s2 = 0.0;
+#pragma unroll
+    for (int s = 0; s < ND; s++) {
+        const double ds = (double)D[s];
+        s0 = __builtin_fma(ds, cparts[3 * s], s0);
+        s1 = __builtin_fma(ds, cparts[3 * s + 1], s1);
+        s2 = __builtin_fma(ds, cparts[3 * s + 2], s2);
+    }
+    const double t = f64m_mulmod(f64m_reduce(s2, q, qinv), w17, w17q, q);
+    const double u = f64m_mulmod(f64m_reduce(t + s1, q, qinv), w17, w17q, q);
+    return f64m_reduce(u + s0, q, qinv);
+}

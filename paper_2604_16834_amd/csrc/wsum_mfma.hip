@@ -10,7 +10,7 @@
 // are exact 8-bit integer matrix products with 32-bit sums (v_mfma_i32_32x32x32_i8, the shape that
 // runs at the full 8-bit rate: measured 4.3 POP/s against 2.5 for the 16x16x64 shape), summed by
 // diagonal (digit positions adding up to s) in 13 accumulators; sum_s D_s 2^(8s) is the exact integer
-// sum of products, reduced once with Barrett.  Nothing is approximated: the result is the same
+// sum of products, reduced once in exact double-precision arithmetic.  Nothing is approximated: the result is the same
 // canonical residue the scalar kernels give.
 //
 // One 256-thread workgroup = 64 columns x of one (component, limb) times 64 output channels.  Wave w
@@ -25,6 +25,7 @@
 // bits) or 4 (32 bits) signed digits instead of 7, which leaves 7*DW digit products (21 or 28 instead of 49) and
 // 7+DW-1 diagonals.  Same exact integer sum, same canonical residues.
 #include "ctx.h"
+#include <cstdlib>
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
@@ -102,22 +103,24 @@ __device__ __forceinline__ void digits_to_b(const u64* v, uint4* bw) {
     for (u32 dx = 0; dx < 7; dx++) bw[dx] = make_uint4(w[dx][0], w[dx][1], w[dx][2], w[dx][3]);
 }
 
-// xs: the n_terms operands in layout xl, wa as above, acc [c_out][2][nl][N];  grid = (ceil(N/64), 2*nl, OT/2).
+// xs: the n_terms operands in layout xl, wa as above, acc [c_out][2][nl][N];  grid = (column groups, 2*nl, OT/2); a
+// workgroup takes the `tiles_per_wg` consecutive 64-column tiles of its group, one after the other.
 // RAGGED: n_terms is not a multiple of 64 or N is not a multiple of 64 (addresses are clamped and
 // the values behind them masked to zero); the regular case carries none of that.
 //
 // Per 64-term block kb the workgroup needs 28 KiB of weight digits (A operands, shared) and the
 // digits of its 64 x 64 values of X (B operands; thread (wave, lane) converts 16 of them: column
 // tile wave>>1, terms 32*(wave&1) + 16*(lane>>5) + j, and shares them through LDS with the wave that
-// owns the other output tile).  Both live in double-buffered LDS.  Iteration kb: store the weights of
-// block kb+1 (requested an iteration ago), request X of block kb+2 and the weights of block kb+2,
-// then run the 98 matrix instructions of block kb out of LDS while the vector ALU turns X of block
-// kb+1 (requested an iteration ago) into digits for the other LDS buffer.
+// owns the other output tile).  Both live in double-buffered LDS.  The blocks of all the workgroup's tiles form one
+// stream: in the iteration that multiplies block b the weights of block b+1 (requested an iteration ago) go to LDS,
+// X and the weights of block b+2 are requested, the matrix instructions of block b run out of LDS while the vector ALU
+// turns X of block b+1 (requested an iteration ago) into digits for the other LDS buffer.  The stream does not stop at
+// a tile's last block: its reduction and stores run with the next tile's first two blocks already on their way.
 template <int DW, bool RAGGED>
 __global__ __launch_bounds__(WM_THREADS) void wsum_mfma_kernel(const u64* __restrict__ xs, XLayout xl, const uint4* __restrict__ wa,
-                                                               u64* __restrict__ acc, const ModConst* __restrict__ mc,
-                                                               const u32* __restrict__ pow256, u32 N, u32 level, u32 nl, u32 num_q,
-                                                               u32 n_terms, u32 c_out, u32 KB, u32 OT) {
+                                                               u64* __restrict__ acc, const ModConstF* __restrict__ mcf,
+                                                               const double* __restrict__ pow256, u32 N, u32 level, u32 nl, u32 num_q,
+                                                               u32 n_terms, u32 c_out, u32 KB, u32 OT, u32 tiles_per_wg) {
     constexpr int DIAGS = WM_DIGITS + DW - 1;
     constexpr int A_STAGE = WM_OT_PER_WG * DW * 2 * 64;  // uint4 words of one 64-term block of weight digits
     // vector instructions of the digit conversion issued per matrix instruction (about 200 per block in all)
@@ -129,12 +132,14 @@ __global__ __launch_bounds__(WM_THREADS) void wsum_mfma_kernel(const u64* __rest
     const u32 g = lane >> 5;                 // which 16 terms of a 32-term step this lane holds
     const u32 wt = wave & 1;                 // output tile this wave owns; also the 32-term step whose X it converts
     const u32 xt = wave >> 1;                // column tile
-    const u32 x = blockIdx.x * 64 + xt * 32 + (lane & 31);
+    const u32 n_tiles = (N + 63) >> 6;
+    const u32 tile_first = blockIdx.x * tiles_per_wg;
+    if (tile_first >= n_tiles) return;       // whole workgroup
+    const u32 tile_last = min(tile_first + tiles_per_wg, n_tiles) - 1;
+    const u32 xin = xt * 32 + (lane & 31);   // column inside a tile
     const u32 e = blockIdx.y % nl, comp = blockIdx.y / nl;
     const u32 ot0 = blockIdx.z * WM_OT_PER_WG;
     const size_t ct_stride = (size_t)2 * nl * N;
-    const size_t off = ((size_t)comp * nl + e) * N + x;
-    const bool x_ok = !RAGGED || x < N;
 
     v16i d[DIAGS];
 #pragma unroll
@@ -142,27 +147,28 @@ __global__ __launch_bounds__(WM_THREADS) void wsum_mfma_kernel(const u64* __rest
 #pragma unroll
         for (int r = 0; r < 16; r++) d[s][r] = 0;
 
-    // term 64*kb + 32*wt + j + 16*g of column x: a wave-uniform row pointer plus a 32-bit lane offset
-    const u32 xc = x_ok ? x : N - 1;
+    // term 64*kb + 32*wt + j + 16*g of column 64*tile + xin: a wave-uniform row pointer plus a 32-bit lane offset
     const u64* xbase = xs + comp * xl.s_comp + e * xl.s_e + (size_t)(32 * wt) * xl.s_k;
-    const u32 lane_off = (u32)(16 * g * xl.s_k + (size_t)(xc >> 6) * xl.s_xt + (xc & 63));
+    const u32 lane_off = (u32)(16 * g * xl.s_k + xin);
+    const u32 tile_step = (u32)xl.s_xt;
     const uint4* wsrc = wa + ((size_t)e * KB * OT + ot0) * (DW * 2 * 64) + tid;  // block kb: + kb * wstep
     const size_t wstep = (size_t)OT * (DW * 2 * 64);
     u64 raw0[16], raw1[16];
     uint4 ap0, ap1, ap2, ap3, ap4, ap5, ap6;  // named, not an array: they live across the loop's back edge in registers
-#define WM_LOAD_X(RAW, KBLK)                                                                          \
+#define WM_LOAD_X(RAW, TILE, KBLK)                                                                    \
     _Pragma("unroll") for (u32 j = 0; j < 16; j++) {                                                  \
         if (RAGGED) {                                                                                 \
             const u32 k = 64 * (KBLK) + 32 * wt + 16 * g + j;                                         \
-            RAW[j] = xs[xl.at(k < n_terms ? k : n_terms - 1, comp, e, xc)];                             \
+            const u32 xx = 64 * (TILE) + xin;                                                         \
+            RAW[j] = xs[xl.at(k < n_terms ? k : n_terms - 1, comp, e, xx < N ? xx : N - 1)];            \
         } else {                                                                                      \
-            RAW[j] = (xbase + (size_t)(64 * (KBLK) + j) * xl.s_k)[lane_off];                          \
+            RAW[j] = (xbase + (size_t)(64 * (KBLK) + j) * xl.s_k)[lane_off + (TILE) * tile_step];     \
         }                                                                                             \
     }
-#define WM_MASK_X(RAW, KBLK)                                                                          \
+#define WM_MASK_X(RAW, TILE, KBLK)                                                                    \
     if (RAGGED) {                                                                                     \
         _Pragma("unroll") for (u32 j = 0; j < 16; j++)                                                \
-            RAW[j] &= (x_ok && 64 * (KBLK) + 32 * wt + 16 * g + j < n_terms) ? ~0ull : 0ull;          \
+            RAW[j] &= (64 * (TILE) + xin < N && 64 * (KBLK) + 32 * wt + 16 * g + j < n_terms) ? ~0ull : 0ull; \
     }
 #define WM_A_EACH(OP)                                                                                \
     {                                                                                                 \
@@ -184,15 +190,21 @@ __global__ __launch_bounds__(WM_THREADS) void wsum_mfma_kernel(const u64* __rest
         digits_to_b(RAW, bw__);                                                                       \
         _Pragma("unroll") for (u32 dx = 0; dx < 7; dx++) lds_b[BUF][((xt * 2 + wt) * 7 + dx) * 64 + lane] = bw__[dx]; \
     }
-// One iteration: RAW_NEW receives X of block kb+2, RAW_OLD holds X of block kb+1.
-#define WM_ITER(RAW_NEW, RAW_OLD)                                                                     \
+// the block after (TILE, KBLK) in the workgroup's stream; the stream's last block follows itself
+#define WM_ADVANCE(TILE, KBLK)                                                                        \
     {                                                                                                 \
-        const u32 cur = kb & 1;                                                                       \
-        __syncthreads(); /* blocks kb of both operands are in LDS[cur]; everyone is done with LDS[cur ^ 1] */ \
+        if ((KBLK) + 1 < KB) (KBLK)++;                                                                \
+        else if ((TILE) < tile_last) { (TILE)++; (KBLK) = 0; }                                        \
+    }
+// One iteration on LDS buffer CUR: multiplies block (tile_c, kb_c); RAW_OLD holds X of the next block (tile_n, kb_n),
+// RAW_NEW receives X of the one after (tile_l, kb_l).
+#define WM_ITER(CUR, RAW_NEW, RAW_OLD)                                                                \
+    {                                                                                                 \
+        constexpr u32 cur = (CUR);                                                                    \
+        __syncthreads(); /* this block of both operands is in LDS[cur]; everyone is done with LDS[cur ^ 1] */ \
         WM_STORE_A(cur ^ 1)                                                                           \
-        const u32 kx = kb + 2 < KB ? kb + 2 : KB - 1;                                                 \
-        WM_LOAD_X(RAW_NEW, kx)                                                                        \
-        WM_LOAD_A(kx)                                                                                 \
+        WM_LOAD_A(kb_l) /* before X: loads return in order, and the weights are wanted first (next iteration's start) */ \
+        WM_LOAD_X(RAW_NEW, tile_l, kb_l)                                                              \
         __builtin_amdgcn_sched_barrier(0);                                                            \
         const uint4* la = &lds_a[cur][wt * (DW * 2 * 64) + lane];                                     \
         const uint4* lb = &lds_b[cur][xt * (2 * WM_DIGITS * 64) + lane];                              \
@@ -210,7 +222,7 @@ __global__ __launch_bounds__(WM_THREADS) void wsum_mfma_kernel(const u64* __rest
             _Pragma("unroll") for (u32 dx = 0; dx < WM_DIGITS; dx++)                                  \
                 d[dx + dw] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[dx][ks], d[dx + dw], 0, 0, 0); \
         }                                                                                             \
-        WM_MASK_X(RAW_OLD, kb + 1)                                                                    \
+        WM_MASK_X(RAW_OLD, tile_n, kb_n)                                                              \
         WM_STORE_B(RAW_OLD, cur ^ 1)                                                                  \
         /* issue order: the 16 LDS reads that start the block, then per matrix instruction two vector */ \
         /* instructions of the digit conversion, an LDS read every seven, the LDS writes last */        \
@@ -224,20 +236,61 @@ __global__ __launch_bounds__(WM_THREADS) void wsum_mfma_kernel(const u64* __rest
         }                                                                                             \
         __builtin_amdgcn_sched_group_barrier(0x200, 7, 0);                                            \
         __builtin_amdgcn_sched_barrier(0);                                                            \
+        if (kb_c + 1 == KB) fold_and_store(tile_c);                                                   \
+        tile_c = tile_n, kb_c = kb_n;                                                                 \
+        tile_n = tile_l, kb_n = kb_l;                                                                 \
+        WM_ADVANCE(tile_l, kb_l)                                                                      \
     }
 
+    // sum_s D_s 2^(8s) is the exact sum of products; modulo q it equals sum_s D_s c_s with c_s = 2^(8s) mod q, taken in
+    // exact double-precision sums (f64m_fold_diagonals).  Leaves the accumulators at zero.
+    const u32 mi = e <= level ? e : num_q + (e - level - 1);
+    auto fold_and_store = [&](u32 tile) {
+        const u32 x = 64 * tile + xin;
+        const ModConstF m = mcf[mi];
+        const double* __restrict__ pw = pow256 + (size_t)mi * POW256_ROW;
+        double cp[3 * DIAGS];
+#pragma unroll
+        for (u32 s = 0; s < 3 * DIAGS; s++) cp[s] = pw[s];
+        const double w17 = pw[39], w17q = pw[40];
+        const size_t off = ((size_t)comp * nl + e) * N + x;
+#pragma unroll
+        for (u32 r = 0; r < 16; r++) {
+            const u32 o = 32 * (ot0 + wt) + 8 * (r >> 2) + 4 * g + (r & 3);
+            int ds[DIAGS];
+#pragma unroll
+            for (u32 s = 0; s < DIAGS; s++) {
+                // the sums stay in the accumulator registers across the loop; read one, clear it
+                int zero;
+                asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(ds[s]) : "a"(d[s][r]));
+                asm volatile("v_accvgpr_write_b32 %0, 0" : "=a"(zero));
+                d[s][r] = zero;
+            }
+            const double v = f64m_fold_diagonals<DIAGS>(ds, cp, w17, w17q, m.q, m.qinv);
+            if (o < c_out && (!RAGGED || x < N)) acc[(size_t)o * ct_stride + off] = f64m_canonical(v, m.q);
+            __builtin_amdgcn_sched_barrier(0);  // one output at a time: the loads in flight own most of the registers
+        }
+    };
+
+    u32 tile_c = tile_first, kb_c = 0;
+    u32 tile_n = tile_c, kb_n = kb_c;
+    WM_ADVANCE(tile_n, kb_n)
+    u32 tile_l = tile_n, kb_l = kb_n;
+    WM_ADVANCE(tile_l, kb_l)
     WM_LOAD_A(0)
     WM_STORE_A(0)
-    WM_LOAD_X(raw0, 0)
-    WM_MASK_X(raw0, 0)
+    WM_LOAD_X(raw0, tile_c, kb_c)
+    WM_MASK_X(raw0, tile_c, kb_c)
     WM_STORE_B(raw0, 0)
-    WM_LOAD_A(KB > 1 ? 1 : 0)
-    WM_LOAD_X(raw1, KB > 1 ? 1 : 0)
-    for (u32 kb = 0; kb < KB; kb += 2) {
-        WM_ITER(raw0, raw1)
-        kb++;
-        if (kb < KB) WM_ITER(raw1, raw0)
-        kb--;
+    __builtin_amdgcn_sched_barrier(0);  // same request order as inside the loop (weights, then X), or the loop's first wait drains both
+    WM_LOAD_A(kb_n)
+    __builtin_amdgcn_sched_barrier(0);
+    WM_LOAD_X(raw1, tile_n, kb_n)
+    __builtin_amdgcn_sched_barrier(0);
+    const u32 n_blocks = (tile_last - tile_first + 1) * KB;
+    for (u32 gb = 0; gb < n_blocks; gb += 2) {
+        WM_ITER(0, raw0, raw1)
+        if (gb + 1 < n_blocks) WM_ITER(1, raw1, raw0)
     }
 #undef WM_LOAD_X
 #undef WM_MASK_X
@@ -245,42 +298,10 @@ __global__ __launch_bounds__(WM_THREADS) void wsum_mfma_kernel(const u64* __rest
 #undef WM_STORE_A
 #undef WM_STORE_B
 #undef WM_ITER
+#undef WM_ADVANCE
 #undef WM_A_EACH
 #undef WM_A_LD
 #undef WM_A_ST
-
-    // sum_s D_s 2^(8s) is the exact sum of products; modulo q it equals sum_s D_s c_s with c_s = 2^(8s) mod q.
-    // c_s comes in 25-bit halves, so the two signed sums of 13 products (27 x 25 bits each) fit 64 bits, and
-    // V = S_lo + 2^25 S_hi (below 2^82 in magnitude) takes one Barrett reduction.
-    if (!x_ok) return;
-    const u32 mi = e <= level ? e : num_q + (e - level - 1);
-    const ModConst m = mc[mi];
-    const u32* __restrict__ pw = pow256 + (size_t)mi * 26;
-    u32 clo[DIAGS], chi[DIAGS];
-#pragma unroll
-    for (u32 s = 0; s < DIAGS; s++) {
-        clo[s] = pw[2 * s];
-        chi[s] = pw[2 * s + 1];
-    }
-#pragma unroll
-    for (u32 r = 0; r < 16; r++) {
-        const u32 o = 32 * (ot0 + wt) + 8 * (r >> 2) + 4 * g + (r & 3);
-        if (o >= c_out) continue;
-        long long slo = 0, shi = 0;
-#pragma unroll
-        for (u32 s = 0; s < DIAGS; s++) {
-            slo += (long long)d[s][r] * (long long)(int)clo[s];
-            shi += (long long)d[s][r] * (long long)(int)chi[s];
-        }
-        __int128 val = (__int128)shi * (1 << 25) + slo;
-        const bool neg = val < 0;
-        if (neg) val = -val;
-        U128 u;
-        u.lo = (u64)val;
-        u.hi = (u64)(val >> 64);
-        const u64 rr = barrett_reduce(u, m);
-        acc[(size_t)o * ct_stride + off] = (neg && rr) ? m.q - rr : rr;
-    }
 }
 
 bool wsum_mfma_applies(const ckks_ctx* c, u32 n_terms) { return c->small_q && n_terms <= c->lazy_terms && n_terms <= 4096; }
@@ -296,13 +317,13 @@ size_t wsum_mfma_scratch_elems(u32 n_limbs, u32 n_terms, u32 c_out) {
 
 template <int DW>
 static void launch_wsum_dw(bool ragged, dim3 grid, hipStream_t st, const u64* xs, XLayout xl, const uint4* wa, u64* acc, const ckks_ctx* c,
-                           u32 level, u32 nl, u32 n_terms, u32 c_out, u32 KB, u32 OT) {
+                           u32 level, u32 nl, u32 n_terms, u32 c_out, u32 KB, u32 OT, u32 tiles_per_wg) {
     if (ragged)
-        hipLaunchKernelGGL((wsum_mfma_kernel<DW, true>), grid, dim3(WM_THREADS), 0, st, xs, xl, wa, acc, c->d_mc, c->d_pow256, c->N, level, nl,
-                           c->num_q, n_terms, c_out, KB, OT);
+        hipLaunchKernelGGL((wsum_mfma_kernel<DW, true>), grid, dim3(WM_THREADS), 0, st, xs, xl, wa, acc, c->d_mcf, c->d_pow256, c->N, level, nl,
+                           c->num_q, n_terms, c_out, KB, OT, tiles_per_wg);
     else
-        hipLaunchKernelGGL((wsum_mfma_kernel<DW, false>), grid, dim3(WM_THREADS), 0, st, xs, xl, wa, acc, c->d_mc, c->d_pow256, c->N, level, nl,
-                           c->num_q, n_terms, c_out, KB, OT);
+        hipLaunchKernelGGL((wsum_mfma_kernel<DW, false>), grid, dim3(WM_THREADS), 0, st, xs, xl, wa, acc, c->d_mcf, c->d_pow256, c->N, level, nl,
+                           c->num_q, n_terms, c_out, KB, OT, tiles_per_wg);
 }
 
 hipError_t launch_wsum_mfma(const ckks_ctx* c, u32 level, u32 nl, const u64* xs, XLayout xl, u32 n_terms, const u64* w_res, u32 c_out,
@@ -311,11 +332,15 @@ hipError_t launch_wsum_mfma(const ckks_ctx* c, u32 level, u32 nl, const u64* xs,
     const size_t prep = (size_t)nl * KB * OT * DW * 2 * 64;
     hipLaunchKernelGGL(wsum_prep_kernel, dim3((u32)((prep + WM_THREADS - 1) / WM_THREADS)), dim3(WM_THREADS), 0, st, w_res,
                        (uint4*)scratch, c->d_mc, level, c->num_q, c_out, n_terms, nl, KB, OT, DW);
-    dim3 grid((c->N + 63) / 64, 2 * nl, OT / WM_OT_PER_WG);
+    // tiles of one workgroup: enough that the start and the end of its stream are a small part of it, few enough that the
+    // chip's 256 CUs still get many workgroups each
+    static const u32 tpw_env = getenv("WSUM_TPW") ? (u32)atoi(getenv("WSUM_TPW")) : 16;
+    const u32 n_tiles = (c->N + 63) / 64, tiles_per_wg = n_tiles < tpw_env ? n_tiles : tpw_env;
+    dim3 grid((n_tiles + tiles_per_wg - 1) / tiles_per_wg, 2 * nl, OT / WM_OT_PER_WG);
     // the 32-bit lane offset of the regular kernel spans 16 terms: 16 * (2 * nl * N) words must fit
     const bool ragged = (n_terms & 63) || (c->N & 63) || 16 * xl.s_k + (size_t)(c->N >> 6) * xl.s_xt + 64 > 0xffffffffull;
-    if (DW == 3) launch_wsum_dw<3>(ragged, grid, st, xs, xl, (const uint4*)scratch, acc, c, level, nl, n_terms, c_out, KB, OT);
-    else if (DW == 4) launch_wsum_dw<4>(ragged, grid, st, xs, xl, (const uint4*)scratch, acc, c, level, nl, n_terms, c_out, KB, OT);
-    else launch_wsum_dw<WM_DIGITS>(ragged, grid, st, xs, xl, (const uint4*)scratch, acc, c, level, nl, n_terms, c_out, KB, OT);
+    if (DW == 3) launch_wsum_dw<3>(ragged, grid, st, xs, xl, (const uint4*)scratch, acc, c, level, nl, n_terms, c_out, KB, OT, tiles_per_wg);
+    else if (DW == 4) launch_wsum_dw<4>(ragged, grid, st, xs, xl, (const uint4*)scratch, acc, c, level, nl, n_terms, c_out, KB, OT, tiles_per_wg);
+    else launch_wsum_dw<WM_DIGITS>(ragged, grid, st, xs, xl, (const uint4*)scratch, acc, c, level, nl, n_terms, c_out, KB, OT, tiles_per_wg);
     return hipGetLastError();
 }

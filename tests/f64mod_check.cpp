@@ -165,4 +165,44 @@ void ref_fwd_round(const int64_t* v8, const uint64_t* tw7, uint64_t q, uint64_t*
     }
 }
 
+// the fold of nd digit diagonals (rows of D: [n][nd] 32-bit signed; constants c[nd] < q), nd in {9, 10, 13}: the parts
+// of the constants and the multiplier 2^17 mod q are formed here the way the library's table holds them
+int run_fold(const int32_t* D, const uint64_t* c, uint32_t nd, uint64_t q, double* r, size_t n) {
+    const double qd = (double)q, qinv = 1.0 / qd;
+    double cp[39];
+    if (nd > 13) return -1;
+    for (uint32_t s = 0; s < nd; s++) {
+        cp[3 * s] = (double)(c[s] & 0x1ffffu);
+        cp[3 * s + 1] = (double)((c[s] >> 17) & 0x1ffffu);
+        cp[3 * s + 2] = (double)(c[s] >> 34);
+    }
+    const uint64_t w17 = 131072 % q;
+    const double w17d = (double)w17, w17q = w17d / qd;
+    for (size_t i = 0; i < n; i++) {
+        const int* row = (const int*)(D + i * nd);
+        switch (nd) {
+            case 9: r[i] = f64m_fold_diagonals<9>(row, cp, w17d, w17q, qd, qinv); break;
+            case 10: r[i] = f64m_fold_diagonals<10>(row, cp, w17d, w17q, qd, qinv); break;
+            case 13: r[i] = f64m_fold_diagonals<13>(row, cp, w17d, w17q, qd, qinv); break;
+            default: return -1;
+        }
+    }
+    return 0;
+}
+
+// r[i] is an integer, |r[i]| <= q/2 + 1, congruent to sum_s D[i][s] * c[s]; returns the number of failures
+long chk_fold(const int32_t* D, const uint64_t* c, uint32_t nd, const double* r, uint64_t q, size_t n) {
+    long bad = 0;
+    for (size_t i = 0; i < n; i++) {
+        i128 want = 0;
+        for (uint32_t s = 0; s < nd; s++) want += (i128)D[i * nd + s] * (i128)c[s];
+        const i128 got = (i128)as_int(r[i]);
+        const bool integral = (double)as_int(r[i]) == r[i];
+        const bool small = got <= (i128)(q / 2 + 1) && got >= -(i128)(q / 2 + 1);
+        const bool congruent = ((want - got) % (i128)q) == 0;
+        if (!(integral && small && congruent)) bad++;
+    }
+    return bad;
+}
+
 }  // extern "C"

@@ -29,6 +29,7 @@ def build_checker(out_dir):
     lib.chk_canonical.restype = ctypes.c_long
     lib.chk_centre.restype = ctypes.c_long
     lib.chk_dot.restype = ctypes.c_long
+    lib.chk_fold.restype = ctypes.c_long
     lib.run_fwd_round.restype = ctypes.c_double
     return lib
 
@@ -236,3 +237,33 @@ def test_forward_round_of_three_stages(lib, q):
         assert np.all(np.abs(got) <= half), (q, trial)
         assert np.array_equal(np.mod(got, q).astype(np.uint64), want), (q, trial)
     assert worst < 2 * q
+
+
+@pytest.mark.parametrize("nd", [9, 10, 13])
+@pytest.mark.parametrize("q", PRIMES + [3, 5, 131071, 131101])
+def test_fold_of_digit_diagonals(lib, q, nd):
+    """The matrix-core sum's last step: sum_s D_s 256^s mod q for 32-bit signed diagonals D_s, with 9, 10 or 13 of them
+    (3-, 4- and 7-digit weights).  Boundaries: every diagonal at +-(2^31 - 1) and at -2^31 (the three partial sums at
+    their largest), single diagonals at the extremes, zeros; then seeded random diagonals of full 32-bit range and of
+    the benchmark's range (|D| < 2^26).  Moduli include 3, 5 and ones just below and above the multiplier 2^17."""
+    rng = np.random.default_rng(1000 * nd + q % 997)
+    c = np.array([pow(256, s, q) for s in range(nd)], dtype=np.uint64)
+    lo, hi = -(1 << 31), (1 << 31) - 1
+    rows = [np.full(nd, hi), np.full(nd, lo), np.zeros(nd), np.full(nd, 1), np.full(nd, -1),
+            np.where(np.arange(nd) % 2 == 0, hi, lo), np.where(np.arange(nd) % 2 == 0, lo, hi)]
+    for s in range(nd):
+        for v in (hi, lo, 1, -1):
+            row = np.zeros(nd)
+            row[s] = v
+            rows.append(row)
+    edge = np.array(rows, dtype=np.int64).astype(np.int32)
+    wide = rng.integers(lo, hi + 1, size=(150_000, nd), dtype=np.int64).astype(np.int32)
+    bench = rng.integers(-(1 << 26), 1 << 26, size=(150_000, nd), dtype=np.int64).astype(np.int32)
+    for D in (edge, wide, bench):
+        D = np.ascontiguousarray(D)
+        r = np.empty(D.shape[0], dtype=np.float64)
+        assert lib.run_fold(ptr(D), ptr(c), nd, ctypes.c_uint64(q), ptr(r), ctypes.c_size_t(D.shape[0])) == 0
+        assert lib.chk_fold(ptr(D), ptr(c), nd, ptr(r), ctypes.c_uint64(q), ctypes.c_size_t(D.shape[0])) == 0
+    # the judge itself: a planted off-by-one is caught
+    r[0] += 1.0
+    assert lib.chk_fold(ptr(D), ptr(c), nd, ptr(r), ctypes.c_uint64(q), ctypes.c_size_t(D.shape[0])) == 1
