@@ -153,16 +153,24 @@ __global__ __launch_bounds__(WM_THREADS) void wsum_mfma_kernel(const u64* __rest
     const u32 tile_step = (u32)xl.s_xt;
     const uint4* wsrc = wa + ((size_t)e * KB * OT + ot0) * (DW * 2 * 64) + tid;  // block kb: + kb * wstep
     const size_t wstep = (size_t)OT * (DW * 2 * 64);
-    u64 raw0[16], raw1[16];
-    uint4 ap0, ap1, ap2, ap3, ap4, ap5, ap6;  // named, not an array: they live across the loop's back edge in registers
+    u64 raw0[16], raw1[16], raw2[16];
+    // named, not arrays: they live across the loop's back edge in registers.  Two sets: the weights of two blocks are on
+    // their way at any time
+    uint4 apA0, apA1, apA2, apA3, apA4, apA5, apA6, apB0, apB1, apB2, apB3, apB4, apB5, apB6;
+// no memory operation moves across this point, in any pass of the compiler
+#define WM_KEEP_ORDER asm volatile("" ::: "memory"); __builtin_amdgcn_sched_barrier(0);
 #define WM_LOAD_X(RAW, TILE, KBLK)                                                                    \
-    _Pragma("unroll") for (u32 j = 0; j < 16; j++) {                                                  \
-        if (RAGGED) {                                                                                 \
+    if (RAGGED) {                                                                                     \
+        _Pragma("unroll") for (u32 j = 0; j < 16; j++) {                                              \
             const u32 k = 64 * (KBLK) + 32 * wt + 16 * g + j;                                         \
             const u32 xx = 64 * (TILE) + xin;                                                         \
             RAW[j] = xs[xl.at(k < n_terms ? k : n_terms - 1, comp, e, xx < N ? xx : N - 1)];            \
-        } else {                                                                                      \
-            RAW[j] = (xbase + (size_t)(64 * (KBLK) + j) * xl.s_k)[lane_off + (TILE) * tile_step];     \
+        }                                                                                             \
+    } else { /* one 64-bit address per block, then one addition per term */                           \
+        const u64* p__ = xbase + ((size_t)(64 * (KBLK)) * xl.s_k + (size_t)(TILE) * tile_step) + lane_off; \
+        _Pragma("unroll") for (u32 j = 0; j < 16; j++) {                                              \
+            RAW[j] = *p__;                                                                            \
+            p__ += xl.s_k;                                                                            \
         }                                                                                             \
     }
 #define WM_MASK_X(RAW, TILE, KBLK)                                                                    \
@@ -170,20 +178,20 @@ __global__ __launch_bounds__(WM_THREADS) void wsum_mfma_kernel(const u64* __rest
         _Pragma("unroll") for (u32 j = 0; j < 16; j++)                                                \
             RAW[j] &= (64 * (TILE) + xin < N && 64 * (KBLK) + 32 * wt + 16 * g + j < n_terms) ? ~0ull : 0ull; \
     }
-#define WM_A_EACH(OP)                                                                                \
+#define WM_A_EACH(OP, S)                                                                             \
     {                                                                                                 \
-        if (DW > 0) OP(0, ap0)                                                                        \
-        if (DW > 1) OP(1, ap1)                                                                        \
-        if (DW > 2) OP(2, ap2)                                                                        \
-        if (DW > 3) OP(3, ap3)                                                                        \
-        if (DW > 4) OP(4, ap4)                                                                        \
-        if (DW > 5) OP(5, ap5)                                                                        \
-        if (DW > 6) OP(6, ap6)                                                                        \
+        if (DW > 0) OP(0, ap##S##0)                                                                   \
+        if (DW > 1) OP(1, ap##S##1)                                                                   \
+        if (DW > 2) OP(2, ap##S##2)                                                                   \
+        if (DW > 3) OP(3, ap##S##3)                                                                   \
+        if (DW > 4) OP(4, ap##S##4)                                                                   \
+        if (DW > 5) OP(5, ap##S##5)                                                                   \
+        if (DW > 6) OP(6, ap##S##6)                                                                   \
     }
 #define WM_A_LD(I, V) { V = wsrc[kblk__ * wstep + I * WM_THREADS]; }
 #define WM_A_ST(I, V) { lds_a[buf__][tid + I * WM_THREADS] = V; }
-#define WM_LOAD_A(KBLK) { const size_t kblk__ = (KBLK); WM_A_EACH(WM_A_LD) }
-#define WM_STORE_A(BUF) { const u32 buf__ = (BUF); WM_A_EACH(WM_A_ST) }
+#define WM_LOAD_A(S, KBLK) { const size_t kblk__ = (KBLK); WM_A_EACH(WM_A_LD, S) }
+#define WM_STORE_A(S, BUF) { const u32 buf__ = (BUF); WM_A_EACH(WM_A_ST, S) }
 #define WM_STORE_B(RAW, BUF)                                                                          \
     {                                                                                                 \
         uint4 bw__[7];                                                                                \
@@ -196,50 +204,75 @@ __global__ __launch_bounds__(WM_THREADS) void wsum_mfma_kernel(const u64* __rest
         if ((KBLK) + 1 < KB) (KBLK)++;                                                                \
         else if ((TILE) < tile_last) { (TILE)++; (KBLK) = 0; }                                        \
     }
-// One iteration on LDS buffer CUR: multiplies block (tile_c, kb_c); RAW_OLD holds X of the next block (tile_n, kb_n),
-// RAW_NEW receives X of the one after (tile_l, kb_l).
-#define WM_ITER(CUR, RAW_NEW, RAW_OLD)                                                                \
+// One iteration on LDS buffer CUR: multiplies block b = (tile_c, kb_c).  On entry the requests of two iterations are
+// outstanding, oldest first: [weights of b+1 (register set S), X of b+1 (RAW_OLD)], [weights of b+2, X of b+2].  The
+// iteration waits for the first pair only (loads return in order), stores those weights to LDS, requests
+// [weights of b+3 (set S again), X of b+3 (RAW_NEW, whose block b was converted an iteration ago)], and runs the matrix
+// instructions of block b while the vector ALU turns X of b+1 into digits: two blocks stay on their way throughout,
+// the tile's last fold and stores included.
+#define WM_ITER(CUR, S, RAW_NEW, RAW_OLD)                                                             \
     {                                                                                                 \
         constexpr u32 cur = (CUR);                                                                    \
         __syncthreads(); /* this block of both operands is in LDS[cur]; everyone is done with LDS[cur ^ 1] */ \
-        WM_STORE_A(cur ^ 1)                                                                           \
-        WM_LOAD_A(kb_l) /* before X: loads return in order, and the weights are wanted first (next iteration's start) */ \
-        WM_LOAD_X(RAW_NEW, tile_l, kb_l)                                                              \
-        __builtin_amdgcn_sched_barrier(0);                                                            \
         const uint4* la = &lds_a[cur][wt * (DW * 2 * 64) + lane];                                     \
         const uint4* lb = &lds_b[cur][xt * (2 * WM_DIGITS * 64) + lane];                              \
-        v4i b[WM_DIGITS][2];                                                                          \
-        _Pragma("unroll") for (u32 ks = 0; ks < 2; ks++)                                              \
-            _Pragma("unroll") for (u32 dx = 0; dx < WM_DIGITS; dx++) {                                \
-                const uint4 t = lb[(ks * WM_DIGITS + dx) * 64];                                       \
-                b[dx][ks] = (v4i){(int)t.x, (int)t.y, (int)t.z, (int)t.w};                            \
-            }                                                                                         \
-        uint4 av = la[0];                                                                             \
-        _Pragma("unroll") for (u32 i = 0; i < DW * 2; i++) {                                          \
-            const u32 dw = i >> 1, ks = i & 1;                                                        \
-            const v4i a = (v4i){(int)av.x, (int)av.y, (int)av.z, (int)av.w};                          \
-            if (i + 1 < DW * 2) av = la[(i + 1) * 64];                                                \
-            _Pragma("unroll") for (u32 dx = 0; dx < WM_DIGITS; dx++)                                  \
-                d[dx + dw] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[dx][ks], d[dx + dw], 0, 0, 0); \
+        /* first the 32-term step ks = 0 with every weight digit, then ks = 1: seven B operands are held at a time; */ \
+        /* the A operand of the next group of seven and, in the last group of ks = 0, the B operands of ks = 1 are */ \
+        /* read from LDS a group (more than the LDS latency) ahead of their use */                     \
+        v4i b[WM_DIGITS], bn[WM_DIGITS];                                                              \
+        uint4 av = la[0], avn = av; /* first: the four waves read at once, and the first instruction needs this one */ \
+        __builtin_amdgcn_sched_barrier(0);                                                            \
+        _Pragma("unroll") for (u32 dx = 0; dx < WM_DIGITS; dx++) {                                    \
+            const uint4 t = lb[dx * 64];                                                              \
+            b[dx] = (v4i){(int)t.x, (int)t.y, (int)t.z, (int)t.w};                                    \
         }                                                                                             \
+        _Pragma("unroll") for (u32 grp = 0; grp < 2 * DW; grp++) {                                    \
+            const u32 dw = grp % DW;                                                                  \
+            if (grp + 1 < 2 * DW) avn = la[(((grp + 1) % DW) * 2 + (grp + 1) / DW) * 64];             \
+            if (grp == DW - 1) {                                                                      \
+                _Pragma("unroll") for (u32 dx = 0; dx < WM_DIGITS; dx++) {                            \
+                    const uint4 t = lb[(WM_DIGITS + dx) * 64];                                        \
+                    bn[dx] = (v4i){(int)t.x, (int)t.y, (int)t.z, (int)t.w};                           \
+                }                                                                                     \
+            }                                                                                         \
+            const v4i a = (v4i){(int)av.x, (int)av.y, (int)av.z, (int)av.w};                          \
+            _Pragma("unroll") for (u32 dx = 0; dx < WM_DIGITS; dx++)                                  \
+                d[dx + dw] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[dx], d[dx + dw], 0, 0, 0);    \
+            av = avn;                                                                                 \
+            if (grp == DW - 1) { _Pragma("unroll") for (u32 dx = 0; dx < WM_DIGITS; dx++) b[dx] = bn[dx]; } \
+        }                                                                                             \
+        /* everything else of the iteration rides between the matrix instructions (see the issue order below) */ \
+        WM_STORE_A(S, cur ^ 1)                                                                        \
+        WM_LOAD_A(S, kb_x)                                                                            \
+        WM_LOAD_X(RAW_NEW, tile_x, kb_x)                                                              \
         WM_MASK_X(RAW_OLD, tile_n, kb_n)                                                              \
         WM_STORE_B(RAW_OLD, cur ^ 1)                                                                  \
-        /* issue order: the 16 LDS reads that start the block, then per matrix instruction two vector */ \
-        /* instructions of the digit conversion, an LDS read every seven, the LDS writes last */        \
-        __builtin_amdgcn_sched_group_barrier(0x100, 16, 0);                                           \
-        _Pragma("unroll") for (u32 i = 0; i < DW * 2; i++) {                                          \
+        /* issue order: the LDS reads that start the block; then per matrix instruction a few vector instructions */ \
+        /* (digit conversion, addresses) and one memory instruction: the stores of the weights to LDS during the */ \
+        /* first group, then the requests of the block three ahead, the stores of the converted digits at the end; */ \
+        /* each group starts with the LDS reads of the next group's operands */                        \
+        __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);                                            \
+        _Pragma("unroll") for (u32 grp = 0; grp < 2 * DW; grp++) {                                    \
+            if (grp == DW - 1) __builtin_amdgcn_sched_group_barrier(0x100, 1 + WM_DIGITS, 0);         \
+            else if (grp + 1 < 2 * DW) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);             \
             _Pragma("unroll") for (u32 q = 0; q < WM_DIGITS; q++) {                                   \
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                                    \
-                __builtin_amdgcn_sched_group_barrier(0x002, VALU_PER_MFMA, 0);                        \
+                if (grp < DW) __builtin_amdgcn_sched_group_barrier(0x002, 2 * VALU_PER_MFMA - 2, 0); \
+                else __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);                               \
+                if (grp == 0 && q < DW) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);            \
+                else if (grp * WM_DIGITS + q < DW + 4 + 16) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0); \
+                else if (grp * WM_DIGITS + q >= DW * WM_DIGITS + 4 && grp * WM_DIGITS + q < DW * WM_DIGITS + 4 + 2 * WM_DIGITS && ((q & 1) == 0)) \
+                    __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);                                \
             }                                                                                         \
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                        \
         }                                                                                             \
         __builtin_amdgcn_sched_group_barrier(0x200, 7, 0);                                            \
         __builtin_amdgcn_sched_barrier(0);                                                            \
-        if (kb_c + 1 == KB) fold_and_store(tile_c);                                                   \
+        if (kb_c + 1 == KB && gb < n_blocks) fold_and_store(tile_c);                                  \
+        gb++;                                                                                         \
         tile_c = tile_n, kb_c = kb_n;                                                                 \
         tile_n = tile_l, kb_n = kb_l;                                                                 \
-        WM_ADVANCE(tile_l, kb_l)                                                                      \
+        tile_l = tile_x, kb_l = kb_x;                                                                 \
+        WM_ADVANCE(tile_x, kb_x)                                                                      \
     }
 
     // sum_s D_s 2^(8s) is the exact sum of products; modulo q it equals sum_s D_s c_s with c_s = 2^(8s) mod q, taken in
@@ -277,22 +310,39 @@ __global__ __launch_bounds__(WM_THREADS) void wsum_mfma_kernel(const u64* __rest
     WM_ADVANCE(tile_n, kb_n)
     u32 tile_l = tile_n, kb_l = kb_n;
     WM_ADVANCE(tile_l, kb_l)
-    WM_LOAD_A(0)
-    WM_STORE_A(0)
+    u32 tile_x = tile_l, kb_x = kb_l;
+    WM_ADVANCE(tile_x, kb_x)
+    WM_LOAD_A(A, 0)
+    WM_STORE_A(A, 0)
     WM_LOAD_X(raw0, tile_c, kb_c)
     WM_MASK_X(raw0, tile_c, kb_c)
     WM_STORE_B(raw0, 0)
-    __builtin_amdgcn_sched_barrier(0);  // same request order as inside the loop (weights, then X), or the loop's first wait drains both
-    WM_LOAD_A(kb_n)
-    __builtin_amdgcn_sched_barrier(0);
+    // the two pairs of requests the loop expects, in its order
+    WM_KEEP_ORDER
+    WM_LOAD_A(B, kb_n)
+    WM_KEEP_ORDER
     WM_LOAD_X(raw1, tile_n, kb_n)
-    __builtin_amdgcn_sched_barrier(0);
+    WM_KEEP_ORDER
+    WM_LOAD_A(A, kb_l)
+    WM_KEEP_ORDER
+    WM_LOAD_X(raw2, tile_l, kb_l)
+    WM_KEEP_ORDER
+    // three register buffers of X, two sets of weights and two LDS buffers: the pattern repeats every six blocks
     const u32 n_blocks = (tile_last - tile_first + 1) * KB;
-    for (u32 gb = 0; gb < n_blocks; gb += 2) {
-        WM_ITER(0, raw0, raw1)
-        if (gb + 1 < n_blocks) WM_ITER(1, raw1, raw0)
-    }
+    // No way out of the loop but its end (an early exit would be one more way into its head for the compiler's account of
+    // outstanding requests, and every wait in the loop would be set for the worst of them): the stream is run to a
+    // multiple of six blocks; the extra iterations repeat the last block into accumulators that are not read again.
+    u32 gb = 0;
+    do {  // at least one block: no branch between the requests above and the loop, so their order stands
+        WM_ITER(0, B, raw0, raw1)
+        WM_ITER(1, A, raw1, raw2)
+        WM_ITER(0, B, raw2, raw0)
+        WM_ITER(1, A, raw0, raw1)
+        WM_ITER(0, B, raw1, raw2)
+        WM_ITER(1, A, raw2, raw0)
+    } while (gb < n_blocks);
 #undef WM_LOAD_X
+#undef WM_KEEP_ORDER
 #undef WM_MASK_X
 #undef WM_LOAD_A
 #undef WM_STORE_A
