@@ -25,7 +25,6 @@
 // bits) or 4 (32 bits) signed digits instead of 7, which leaves 7*DW digit products (21 or 28 instead of 49) and
 // 7+DW-1 diagonals.  Same exact integer sum, same canonical residues.
 #include "ctx.h"
-#include <cstdlib>
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
@@ -33,6 +32,7 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 #define WM_THREADS 256
 #define WM_DIGITS 7                                     // digits of an X value
 #define WM_BIAS 0x0080808080808080ull
+#define WM_TILES_PER_WG 16                              // 64-column tiles a workgroup streams one after the other
 #define WM_OT_PER_WG 2                                  // output tiles of 32 channels per workgroup
 #define WM_B_STAGE (WM_OT_PER_WG * WM_DIGITS * 2 * 64)  // uint4 words of one 64-term block of X digits (28 KiB)
 
@@ -112,10 +112,10 @@ __device__ __forceinline__ void digits_to_b(const u64* v, uint4* bw) {
 // digits of its 64 x 64 values of X (B operands; thread (wave, lane) converts 16 of them: column
 // tile wave>>1, terms 32*(wave&1) + 16*(lane>>5) + j, and shares them through LDS with the wave that
 // owns the other output tile).  Both live in double-buffered LDS.  The blocks of all the workgroup's tiles form one
-// stream: in the iteration that multiplies block b the weights of block b+1 (requested an iteration ago) go to LDS,
-// X and the weights of block b+2 are requested, the matrix instructions of block b run out of LDS while the vector ALU
-// turns X of block b+1 (requested an iteration ago) into digits for the other LDS buffer.  The stream does not stop at
-// a tile's last block: its reduction and stores run with the next tile's first two blocks already on their way.
+// stream: the iteration that multiplies block b stores the weights of block b+1 to LDS, requests the weights and X of
+// block b+3, and runs the matrix instructions of block b out of LDS while the vector ALU turns X of block b+1 into
+// digits for the other LDS buffer; what it waits for was requested two iterations ago.  The stream does not stop at a
+// tile's last block: its reduction and stores run with the next tile's blocks already on their way.
 template <int DW, bool RAGGED>
 __global__ __launch_bounds__(WM_THREADS) void wsum_mfma_kernel(const u64* __restrict__ xs, XLayout xl, const uint4* __restrict__ wa,
                                                                u64* __restrict__ acc, const ModConstF* __restrict__ mcf,
@@ -383,9 +383,8 @@ hipError_t launch_wsum_mfma(const ckks_ctx* c, u32 level, u32 nl, const u64* xs,
     hipLaunchKernelGGL(wsum_prep_kernel, dim3((u32)((prep + WM_THREADS - 1) / WM_THREADS)), dim3(WM_THREADS), 0, st, w_res,
                        (uint4*)scratch, c->d_mc, level, c->num_q, c_out, n_terms, nl, KB, OT, DW);
     // tiles of one workgroup: enough that the start and the end of its stream are a small part of it, few enough that the
-    // chip's 256 CUs still get many workgroups each
-    static const u32 tpw_env = getenv("WSUM_TPW") ? (u32)atoi(getenv("WSUM_TPW")) : 16;
-    const u32 n_tiles = (c->N + 63) / 64, tiles_per_wg = n_tiles < tpw_env ? n_tiles : tpw_env;
+    // chip's 256 CUs still get many workgroups each (16 tiles: 4096 workgroups at N = 2^16 and 32 limbs)
+    const u32 n_tiles = (c->N + 63) / 64, tiles_per_wg = n_tiles < WM_TILES_PER_WG ? n_tiles : WM_TILES_PER_WG;
     dim3 grid((n_tiles + tiles_per_wg - 1) / tiles_per_wg, 2 * nl, OT / WM_OT_PER_WG);
     // the 32-bit lane offset of the regular kernel spans 16 terms: 16 * (2 * nl * N) words must fit
     const bool ragged = (n_terms & 63) || (c->N & 63) || 16 * xl.s_k + (size_t)(c->N >> 6) * xl.s_xt + 64 > 0xffffffffull;
