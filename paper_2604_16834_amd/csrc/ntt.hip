@@ -260,7 +260,11 @@ __device__ __forceinline__ u64* item_dst(const NttArgs& args, const PolyList& pl
     return args.dst + (((size_t)b * args.dst_bstride + pl.dpos[a]) << args.log_n);
 }
 
-template <class A, int IT, bool EPI>
+// EM (with EPI): which of the optional operands of the division's last step the launch has: 0 = look at each item's pointers,
+// 1 = every item has its addend and nothing else, 2 = none has any.  In cases 1 and 2 the step is straight-line code and the
+// addend is requested with v, a round ahead of its use; behind a condition the compiler keeps each request next to its use, one
+// round trip to memory per point.
+template <class A, int IT, bool EPI, int EM = 0>
 __device__ __forceinline__ void fwd_lo_body(const NttArgs& args, const PolyList& pl, const FwdEpilogue& ep) {
     typedef typename A::E E;
     __shared__ E lds0[LDS_PADDED_WORDS];
@@ -327,9 +331,18 @@ __device__ __forceinline__ void fwd_lo_body(const NttArgs& args, const PolyList&
         __syncthreads();
 #pragma unroll
         for (int j = 0; j < 8; j++) v[j] = buf0[LDS_PAD(8 * tid + j)];
-        u64 vv[8], vv2[8];
+        u64 vv[8], vv2[8], av[8];
         if (EPI) {  // what the results are subtracted from: requested now, needed after the last round
             const u32 bv = b0 + it;
+            if (EM == 1) {  // and the addend (gathered through the item's automorphism)
+                const FinalItem& fa = ep.B.it[bv >> 1];
+                const u64* add = ((bv & 1) ? fa.add1 : fa.add0) + ((size_t)pl.dpos[tile.a] << args.log_n);
+#pragma unroll
+                for (int j = 0; j < 8; j++) {
+                    const u32 x = (u32)off + tid + 256 * j;
+                    av[j] = add[fa.g == 1 ? x : galois_gather_index(x, fa.g, args.log_n)];
+                }
+            }
             const u64* vrow = (ep.use_vl ? ep.vl.p[bv >> 1] + (bv & 1) * ep.v_cstride + ((size_t)pl.dpos[tile.a] << args.log_n)
                                          : ep.v + (((size_t)bv * ep.E + pl.dpos[tile.a]) << args.log_n)) + off;
 #pragma unroll
@@ -378,13 +391,17 @@ __device__ __forceinline__ void fwd_lo_body(const NttArgs& args, const PolyList&
                 for (int j = 0; j < 8; j++) {
                     const u32 p = tid + 256 * j;
                     double r = A::mulmod(vd[j] - buf1[LDS_PAD(p)], cvd, cvq, q);
-                    if (add) {
-                        const u32 x = (u32)off + p;
-                        const u32 xs = fi.g == 1 ? x : galois_gather_index(x, fi.g, args.log_n);
-                        r = A::reduce(r + A::from_u64(add[((size_t)i << args.log_n) + xs]), P.mc);
+                    if (EM == 1) {
+                        r = A::reduce(r + A::from_u64(av[j]), P.mc);
+                    } else if (EM == 0) {
+                        if (add) {
+                            const u32 x = (u32)off + p;
+                            const u32 xs = fi.g == 1 ? x : galois_gather_index(x, fi.g, args.log_n);
+                            r = A::reduce(r + A::from_u64(add[((size_t)i << args.log_n) + xs]), P.mc);
+                        }
+                        if (fi.mask) r = A::mulmod_any(r, A::from_u64(fi.mask[((size_t)i << args.log_n) + off + p]), q, P.mc.qinv);
+                        if (fi.acc) r = A::reduce(r + A::from_u64(fi.acc[(((size_t)comp * ep.n_out + i) << args.log_n) + off + p]), P.mc);
                     }
-                    if (fi.mask) r = A::mulmod_any(r, A::from_u64(fi.mask[((size_t)i << args.log_n) + off + p]), q, P.mc.qinv);
-                    if (fi.acc) r = A::reduce(r + A::from_u64(fi.acc[(((size_t)comp * ep.n_out + i) << args.log_n) + off + p]), P.mc);
                     orow[p] = A::canonical(r, P.mc);
                 }
             } else {
@@ -395,13 +412,17 @@ __device__ __forceinline__ void fwd_lo_body(const NttArgs& args, const PolyList&
                     const u32 p = tid + 256 * j;
                     const u64 w = A::store_fwd_final(buf1[LDS_PAD(p)], P.mc);
                     u64 r = mul_shoup(sub_mod(vv[j], w, mi.q), cv, cvs, mi.q);
-                    if (add) {
-                        const u32 x = (u32)off + p;
-                        const u32 xs = fi.g == 1 ? x : galois_gather_index(x, fi.g, args.log_n);
-                        r = add_mod(r, add[((size_t)i << args.log_n) + xs], mi.q);
+                    if (EM == 1) {
+                        r = add_mod(r, av[j], mi.q);
+                    } else if (EM == 0) {
+                        if (add) {
+                            const u32 x = (u32)off + p;
+                            const u32 xs = fi.g == 1 ? x : galois_gather_index(x, fi.g, args.log_n);
+                            r = add_mod(r, add[((size_t)i << args.log_n) + xs], mi.q);
+                        }
+                        if (fi.mask) r = mulmod_barrett(r, fi.mask[((size_t)i << args.log_n) + off + p], mi);
+                        if (fi.acc) r = add_mod(r, fi.acc[(((size_t)comp * ep.n_out + i) << args.log_n) + off + p], mi.q);
                     }
-                    if (fi.mask) r = mulmod_barrett(r, fi.mask[((size_t)i << args.log_n) + off + p], mi);
-                    if (fi.acc) r = add_mod(r, fi.acc[(((size_t)comp * ep.n_out + i) << args.log_n) + off + p], mi.q);
                     orow[p] = r;
                 }
             }
@@ -416,9 +437,9 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_kernel(NttArgs args, P
 }
 
 // the lo pass as the last kernel of a division by dropped moduli
-template <class A, int IT>
+template <class A, int IT, int EM>
 __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_div_kernel(NttArgs args, PolyList pl, FwdEpilogue ep) {
-    fwd_lo_body<A, IT, true>(args, pl, ep);
+    fwd_lo_body<A, IT, true, EM>(args, pl, ep);
 }
 
 // The lo pass of ModUp's forward transforms with the inner product with the switching key in place of its stores.
@@ -447,6 +468,10 @@ struct MacEpilogue {
     u64 ka[CKKS_MAX_MODULI], kb[CKKS_MAX_MODULI];
 };
 
+// PROD, LIN: ep.prod, ep.lin.  ADD: 0 = no addends, 1 = every batch item has both, 2 = look at the pointers.  They are
+// template arguments so that what follows the digits is straight-line code: with the operands behind conditions, even ones that
+// are the same for the whole launch, the compiler keeps each request next to its use, one round trip to memory per point.
+template <bool PROD, int ADD, bool LIN>
 __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_mac_kernel(NttArgs args, PolyList pl, MacEpilogue ep) {
     typedef ArithF64 A;
     typedef double E;
@@ -535,57 +560,86 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_mac_kernel(NttArgs arg
         }
         j = jn;
     }
-    if (e <= ep.level && ep.prod) {
+    if (PROD && e <= ep.level) {
         // the tensor product of this slice, formed here: d2 feeds the digit that owns the limb, P d0 and P d1 join the sums
         const u64* kj = key + (size_t)own * 2 * kstride;
         const size_t po = (size_t)e * N + off;
         const u64 *pa0 = ep.a0.p[b] + po, *pa1 = ep.a1.p[b] + po, *pb0 = ep.b0.p[b] + po, *pb1 = ep.b1.p[b] + po;
-        const u64* c0 = ep.add0.p[b];
-        const u64* c1 = ep.add1.p[b];
+        const u64* c0 = ADD ? ep.add0.p[b] : nullptr;
+        const u64* c1 = ADD ? ep.add1.p[b] : nullptr;
         const double pres = mc.q - A::from_u64(ep.negp[e]);  // P mod q_e
-        const u64* lx = ep.lin ? ep.lx.p[b] + po : nullptr;
-        const u64* ly = ep.lin ? ep.ly.p[b] + po : nullptr;
-        const double ka = ep.lin ? A::from_u64(ep.ka[e]) : 0.0, kb = ep.lin ? A::from_u64(ep.kb[e]) : 0.0;
+        const u64* lx = LIN ? ep.lx.p[b] + po : nullptr;
+        const u64* ly = LIN ? ep.ly.p[b] + po : nullptr;
+        const double ka = LIN ? A::from_u64(ep.ka[e]) : 0.0, kb = LIN ? A::from_u64(ep.kb[e]) : 0.0;
+#pragma unroll
+        for (int h = 0; h < 8; h += 4) {  // four points at a time: up to ten operands per point, requested before the first is used
+            u64 ra0[4], ra1[4], rb0[4], rb1[4], rk0[4], rk1[4], rc0[4], rc1[4], rx0[4], rx1[4], ry0[4], ry1[4];
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                const u32 x = tid + 256 * (h + i);
+                ra0[i] = pa0[x], ra1[i] = pa1[x], rb0[i] = pb0[x], rb1[i] = pb1[x];
+                rk0[i] = kj[x], rk1[i] = kj[kstride + x];
+                if (ADD == 1) rc0[i] = c0[po + x], rc1[i] = c1[po + x];
+                if (LIN) rx0[i] = lx[x], rx1[i] = lx[ep.x_cstride + x], ry0[i] = ly[x], ry1[i] = ly[ep.y_cstride + x];
+            }
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                const u32 x = tid + 256 * (h + i);
+                const double A0 = A::from_u64(ra0[i]), A1 = A::from_u64(ra1[i]), B0 = A::from_u64(rb0[i]), B1 = A::from_u64(rb1[i]);
+                const double dd2 = A::mulmod_any(A1, B1, mc.q, mc.qinv);
+                double dd0 = A::mulmod_any(A0, B0, mc.q, mc.qinv);
+                double dd1 = A::mulmod_any(A0, B1, mc.q, mc.qinv) + A::mulmod_any(A1, B0, mc.q, mc.qinv);
+                if (ADD == 1) {
+                    dd0 += A::from_u64(rc0[i]);
+                    dd1 += A::from_u64(rc1[i]);
+                } else if (ADD == 2) {
+                    if (c0) dd0 += A::from_u64(c0[po + x]);
+                    if (c1) dd1 += A::from_u64(c1[po + x]);
+                }
+                if (LIN) {  // at most 0.75 q more per term: both sums stay below 2^53
+                    dd0 += A::mulmod_any(A::from_u64(rx0[i]), ka, mc.q, mc.qinv) + A::mulmod_any(A::from_u64(ry0[i]), kb, mc.q, mc.qinv);
+                    dd1 += A::mulmod_any(A::from_u64(rx1[i]), ka, mc.q, mc.qinv) + A::mulmod_any(A::from_u64(ry1[i]), kb, mc.q, mc.qinv);
+                }
+                dd0 = A::reduce(dd0, mc);  // back below q / 2 + 1 as multiplicands
+                dd1 = A::reduce(dd1, mc);
+                acc0[h + i] += A::mulmod_any(dd2, A::from_u64(rk0[i]), mc.q, mc.qinv) + A::mulmod_any(dd0, pres, mc.q, mc.qinv);
+                acc1[h + i] += A::mulmod_any(dd2, A::from_u64(rk1[i]), mc.q, mc.qinv) + A::mulmod_any(dd1, pres, mc.q, mc.qinv);
+            }
+        }
+    } else if (!PROD && e <= ep.level) {
+        // the digit that owns this limb, and P times the optional addends
+        const u64* kj = key + (size_t)own * 2 * kstride;
+        const u64* yo = ep.D.own.p[b] + (size_t)e * N + off;
+        const double pres = mc.q - A::from_u64(ep.negp[e]);  // P mod q_e
+        const u64* a0 = ADD ? ep.add0.p[b] : nullptr;
+        const u64* a1 = ADD ? ep.add1.p[b] : nullptr;
+        const size_t po = (size_t)e * N + off;
+        u64 ry[8], rk0[8], rk1[8], r0[8], r1[8];
 #pragma unroll
         for (int i = 0; i < 8; i++) {
             const u32 x = tid + 256 * i;
-            const double A0 = A::from_u64(pa0[x]), A1 = A::from_u64(pa1[x]), B0 = A::from_u64(pb0[x]), B1 = A::from_u64(pb1[x]);
-            const double dd2 = A::mulmod_any(A1, B1, mc.q, mc.qinv);
-            double dd0 = A::mulmod_any(A0, B0, mc.q, mc.qinv);
-            double dd1 = A::mulmod_any(A0, B1, mc.q, mc.qinv) + A::mulmod_any(A1, B0, mc.q, mc.qinv);
-            if (c0) dd0 += A::from_u64(c0[po + x]);
-            if (c1) dd1 += A::from_u64(c1[po + x]);
-            if (lx) {  // at most 0.75 q more per term: both sums stay below 2^53
-                dd0 += A::mulmod_any(A::from_u64(lx[x]), ka, mc.q, mc.qinv) + A::mulmod_any(A::from_u64(ly[x]), kb, mc.q, mc.qinv);
-                dd1 += A::mulmod_any(A::from_u64(lx[ep.x_cstride + x]), ka, mc.q, mc.qinv) +
-                       A::mulmod_any(A::from_u64(ly[ep.y_cstride + x]), kb, mc.q, mc.qinv);
-            }
-            dd0 = A::reduce(dd0, mc);  // back below q / 2 + 1 as multiplicands
-            dd1 = A::reduce(dd1, mc);
-            acc0[i] += A::mulmod_any(dd2, A::from_u64(kj[x]), mc.q, mc.qinv) + A::mulmod_any(dd0, pres, mc.q, mc.qinv);
-            acc1[i] += A::mulmod_any(dd2, A::from_u64(kj[kstride + x]), mc.q, mc.qinv) + A::mulmod_any(dd1, pres, mc.q, mc.qinv);
+            ry[i] = yo[x], rk0[i] = kj[x], rk1[i] = kj[kstride + x];
+            if (ADD == 1) r0[i] = a0[po + x], r1[i] = a1[po + x];
         }
-    } else if (e <= ep.level) {
-        {  // the digit that owns this limb
-            const u64* kj = key + (size_t)own * 2 * kstride;
-            const u64* yo = ep.D.own.p[b] + (size_t)e * N + off;
 #pragma unroll
-            for (int i = 0; i < 8; i++) {
-                const double y = A::from_u64(yo[tid + 256 * i]);
-                acc0[i] += A::mulmod_any(y, A::from_u64(kj[tid + 256 * i]), mc.q, mc.qinv);
-                acc1[i] += A::mulmod_any(y, A::from_u64(kj[kstride + tid + 256 * i]), mc.q, mc.qinv);
+        for (int i = 0; i < 8; i++) {
+            const double y = A::from_u64(ry[i]);
+            acc0[i] += A::mulmod_any(y, A::from_u64(rk0[i]), mc.q, mc.qinv);
+            acc1[i] += A::mulmod_any(y, A::from_u64(rk1[i]), mc.q, mc.qinv);
+            if (ADD == 1) {
+                acc0[i] += A::mulmod_any(A::from_u64(r0[i]), pres, mc.q, mc.qinv);
+                acc1[i] += A::mulmod_any(A::from_u64(r1[i]), pres, mc.q, mc.qinv);
             }
         }
-        const double pres = mc.q - A::from_u64(ep.negp[e]);  // P mod q_e
-        const u64* a0 = ep.add0.p[b];
-        const u64* a1 = ep.add1.p[b];
-        if (a0) {
+        if (ADD == 2) {
+            if (a0) {
 #pragma unroll
-            for (int i = 0; i < 8; i++) acc0[i] += A::mulmod_any(A::from_u64(a0[(size_t)e * N + off + tid + 256 * i]), pres, mc.q, mc.qinv);
-        }
-        if (a1) {
+                for (int i = 0; i < 8; i++) acc0[i] += A::mulmod_any(A::from_u64(a0[po + tid + 256 * i]), pres, mc.q, mc.qinv);
+            }
+            if (a1) {
 #pragma unroll
-            for (int i = 0; i < 8; i++) acc1[i] += A::mulmod_any(A::from_u64(a1[(size_t)e * N + off + tid + 256 * i]), pres, mc.q, mc.qinv);
+                for (int i = 0; i < 8; i++) acc1[i] += A::mulmod_any(A::from_u64(a1[po + tid + 256 * i]), pres, mc.q, mc.qinv);
+            }
         }
     }
     u64* o0 = ep.out.p[b] + (size_t)e * N + off;
@@ -977,8 +1031,26 @@ static void launch_lo_it(bool inverse, dim3 grid, hipStream_t st, const NttArgs&
 }
 template <class A>
 static void launch_lo_div(u32 items, dim3 grid, hipStream_t st, const NttArgs& args, const PolyList& pl, const FwdEpilogue& ep) {
-    if (items == 2) hipLaunchKernelGGL((ntt_fwd_lo_div_kernel<A, 2>), grid, dim3(NTT_THREADS), 0, st, args, pl, ep);
-    else hipLaunchKernelGGL((ntt_fwd_lo_div_kernel<A, 1>), grid, dim3(NTT_THREADS), 0, st, args, pl, ep);
+    // which optional operands the division's last step has is the same for the whole launch: one instantiation per case
+    u32 n_add = 0, n_other = 0;
+    const u32 n_ct = (args.batch + 1) / 2;
+    for (u32 r = 0; r < n_ct; r++) {
+        const FinalItem& fi = ep.B.it[r];
+        n_add += (fi.add0 ? 1 : 0) + (fi.add1 ? 1 : 0);
+        n_other += (fi.mask ? 1 : 0) + (fi.acc ? 1 : 0);
+    }
+    const int em = n_other ? 0 : (n_add == 2 * n_ct ? 1 : (n_add == 0 ? 2 : 0));
+#define LO_DIV_LAUNCH(IT, EM) hipLaunchKernelGGL((ntt_fwd_lo_div_kernel<A, IT, EM>), grid, dim3(NTT_THREADS), 0, st, args, pl, ep)
+    if (items == 2) {
+        if (em == 1) LO_DIV_LAUNCH(2, 1);
+        else if (em == 2) LO_DIV_LAUNCH(2, 2);
+        else LO_DIV_LAUNCH(2, 0);
+    } else {
+        if (em == 1) LO_DIV_LAUNCH(1, 1);
+        else if (em == 2) LO_DIV_LAUNCH(1, 2);
+        else LO_DIV_LAUNCH(1, 0);
+    }
+#undef LO_DIV_LAUNCH
 }
 template <class A>
 static void launch_lo(bool inverse, u32 items, dim3 grid, hipStream_t st, const NttArgs& args, const PolyList& pl, bool mul = false) {
@@ -1215,7 +1287,22 @@ hipError_t launch_ntt_lo_mac(const ckks_ctx* c, u32 level, const DigitSrc& digit
     if (ep.lin) n_add = 4.0 * n;  // two components of two ciphertexts
     ProfScope ps__(c, K_NTT_FWD_LO, st, 8.0 * c->N * (n * (n_tr + (prod ? 4.0 : 1.0) * (level + 1.0) + 2.0 * E) + n_add * (level + 1.0) + n_keys * 2.0 * beta * E),
                    0.5 * n * n_tr * c->N * c->log_lo);
-    hipLaunchKernelGGL(ntt_fwd_lo_mac_kernel, grid, dim3(NTT_THREADS), 0, st, args, pl, ep);
+    // which operands join after the digits is the same for the whole launch: one instantiation per case
+    u32 with0 = 0, with1 = 0;
+    for (u32 b = 0; b < n; b++) with0 += ep.add0.p[b] ? 1 : 0, with1 += ep.add1.p[b] ? 1 : 0;
+    const int addm = (with0 == 0 && with1 == 0) ? 0 : ((with0 == n && with1 == n) ? 1 : 2);
+#define LO_MAC_LAUNCH(PROD, ADD, LIN) hipLaunchKernelGGL((ntt_fwd_lo_mac_kernel<PROD, ADD, LIN>), grid, dim3(NTT_THREADS), 0, st, args, pl, ep)
+    if (ep.lin) LO_MAC_LAUNCH(true, 0, true);  // the linear combination excludes addends (checked above)
+    else if (ep.prod) {
+        if (addm == 0) LO_MAC_LAUNCH(true, 0, false);
+        else if (addm == 1) LO_MAC_LAUNCH(true, 1, false);
+        else LO_MAC_LAUNCH(true, 2, false);
+    } else {
+        if (addm == 0) LO_MAC_LAUNCH(false, 0, false);
+        else if (addm == 1) LO_MAC_LAUNCH(false, 1, false);
+        else LO_MAC_LAUNCH(false, 2, false);
+    }
+#undef LO_MAC_LAUNCH
     return hipGetLastError();
 }
 
