@@ -220,6 +220,14 @@ __device__ __forceinline__ LoTile lo_tile(u32 log_hi, u32 grp) {
     return r;
 }
 
+// Entry i of one of a PolyList's byte arrays.  The list is a kernel argument and i is the same for the whole workgroup: read
+// as the 32-bit word that holds it, this is a scalar load; a byte load is a vector load whose round trip to memory every
+// address of the kernel then waits for.
+__device__ __forceinline__ u32 pl_at(const unsigned char* arr, u32 i) {
+    const u32 w = reinterpret_cast<const u32*>(arr)[i >> 2];
+    return (w >> (8 * (i & 3))) & 0xffu;
+}
+
 template <class A>
 struct PolyRef {
     const u64* src;
@@ -228,12 +236,15 @@ struct PolyRef {
     typename A::MC mc;
 };
 
-template <class A>
+// BYTES: read the list's entries with byte loads all the same (the converting hi pass: with scalar positions its tables of
+// constants become scalar loads too, four limbs' worth of them more than the scalar registers hold: measured slower)
+template <class A, bool BYTES = false>
 __device__ __forceinline__ PolyRef<A> poly_ref(const NttArgs& args, const PolyList& pl, u32 b, u32 a) {
-    const u32 m_idx = pl.mod[a];
+    const u32 m_idx = BYTES ? pl.mod[a] : pl_at(pl.mod, a);
     PolyRef<A> r;
-    r.src = (args.use_src_list ? args.src_list.p[b] : args.src + (((size_t)b * args.src_bstride) << args.log_n)) + ((size_t)pl.spos[a] << args.log_n);
-    r.dst = args.dst + (((size_t)b * args.dst_bstride + pl.dpos[a]) << args.log_n);
+    const u32 sp = BYTES ? pl.spos[a] : pl_at(pl.spos, a), dp = BYTES ? pl.dpos[a] : pl_at(pl.dpos, a);
+    r.src = (args.use_src_list ? args.src_list.p[b] : args.src + (((size_t)b * args.src_bstride) << args.log_n)) + ((size_t)sp << args.log_n);
+    r.dst = args.dst + (((size_t)b * args.dst_bstride + dp) << args.log_n);
     r.tw = (const typename A::TW*)args.tw + ((size_t)m_idx << args.log_n);
     r.mc = ((const typename A::MC*)args.mc)[m_idx];
     return r;
@@ -254,10 +265,10 @@ __device__ __forceinline__ PolyRef<A> poly_ref(const NttArgs& args, const PolyLi
 // roles from one item to the next.
 template <class A>
 __device__ __forceinline__ const u64* item_src(const NttArgs& args, const PolyList& pl, u32 b, u32 a) {
-    return (args.use_src_list ? args.src_list.p[b] : args.src + (((size_t)b * args.src_bstride) << args.log_n)) + ((size_t)pl.spos[a] << args.log_n);
+    return (args.use_src_list ? args.src_list.p[b] : args.src + (((size_t)b * args.src_bstride) << args.log_n)) + ((size_t)pl_at(pl.spos, a) << args.log_n);
 }
 __device__ __forceinline__ u64* item_dst(const NttArgs& args, const PolyList& pl, u32 b, u32 a) {
-    return args.dst + (((size_t)b * args.dst_bstride + pl.dpos[a]) << args.log_n);
+    return args.dst + (((size_t)b * args.dst_bstride + pl_at(pl.dpos, a)) << args.log_n);
 }
 
 // EM (with EPI): which of the optional operands of the division's last step the launch has: 0 = look at each item's pointers,
@@ -336,20 +347,20 @@ __device__ __forceinline__ void fwd_lo_body(const NttArgs& args, const PolyList&
             const u32 bv = b0 + it;
             if (EM == 1) {  // and the addend (gathered through the item's automorphism)
                 const FinalItem& fa = ep.B.it[bv >> 1];
-                const u64* add = ((bv & 1) ? fa.add1 : fa.add0) + ((size_t)pl.dpos[tile.a] << args.log_n);
+                const u64* add = ((bv & 1) ? fa.add1 : fa.add0) + ((size_t)pl_at(pl.dpos, tile.a) << args.log_n);
 #pragma unroll
                 for (int j = 0; j < 8; j++) {
                     const u32 x = (u32)off + tid + 256 * j;
                     av[j] = add[fa.g == 1 ? x : galois_gather_index(x, fa.g, args.log_n)];
                 }
             }
-            const u64* vrow = (ep.use_vl ? ep.vl.p[bv >> 1] + (bv & 1) * ep.v_cstride + ((size_t)pl.dpos[tile.a] << args.log_n)
-                                         : ep.v + (((size_t)bv * ep.E + pl.dpos[tile.a]) << args.log_n)) + off;
+            const u64* vrow = (ep.use_vl ? ep.vl.p[bv >> 1] + (bv & 1) * ep.v_cstride + ((size_t)pl_at(pl.dpos, tile.a) << args.log_n)
+                                         : ep.v + (((size_t)bv * ep.E + pl_at(pl.dpos, tile.a)) << args.log_n)) + off;
 #pragma unroll
             for (int j = 0; j < 8; j++) vv[j] = vrow[tid + 256 * j];
             if constexpr (std::is_same<A, ArithF64>::value) {
                 if (ep.use_vl == 2) {
-                    const u64* vrow2 = ep.vl2.p[bv >> 1] + (bv & 1) * ep.v2_cstride + ((size_t)pl.dpos[tile.a] << args.log_n) + off;
+                    const u64* vrow2 = ep.vl2.p[bv >> 1] + (bv & 1) * ep.v2_cstride + ((size_t)pl_at(pl.dpos, tile.a) << args.log_n) + off;
 #pragma unroll
                     for (int j = 0; j < 8; j++) vv2[j] = vrow2[tid + 256 * j];
                 }
@@ -368,7 +379,7 @@ __device__ __forceinline__ void fwd_lo_body(const NttArgs& args, const PolyList&
             for (int j = 0; j < 8; j++) dst[tid + 256 * j] = A::store_fwd_final(buf1[LDS_PAD(tid + 256 * j)], P.mc);
         } else {
             // the division's last step on the results w, which are not stored: out = ((v - w) * cinv + addend) * mask
-            const u32 i = pl.dpos[tile.a], bb = b0 + it, comp = bb & 1;
+            const u32 i = pl_at(pl.dpos, tile.a), bb = b0 + it, comp = bb & 1;
             const FinalItem fi = ep.B.it[bb >> 1];
             const u64 cv = ep.cinv[i];
             const u64* add = comp ? fi.add1 : fi.add0;
@@ -405,7 +416,7 @@ __device__ __forceinline__ void fwd_lo_body(const NttArgs& args, const PolyList&
                     orow[p] = A::canonical(r, P.mc);
                 }
             } else {
-                const ModConst mi = ep.mci[pl.mod[tile.a]];
+                const ModConst mi = ep.mci[pl_at(pl.mod, tile.a)];
                 const u64 cvs = ep.cinv[ep.num_q + i];
 #pragma unroll
                 for (int j = 0; j < 8; j++) {
@@ -479,7 +490,7 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_mac_kernel(NttArgs arg
     __shared__ E lds1[LDS_PADDED_WORDS];
     const u32 tid = threadIdx.x;
     const LoTile tile = lo_tile(args.log_hi, args.lo_group);
-    const u32 blk = tile.blk, b = tile.b, e = tile.a, m_idx = pl.mod[e];
+    const u32 blk = tile.blk, b = tile.b, e = tile.a, m_idx = pl_at(pl.mod, e);
     const size_t N = (size_t)1 << args.log_n, off = (size_t)blk << 11;
     const TwF* tw = (const TwF*)args.tw + ((size_t)m_idx << args.log_n);
     const ModConstF mc = ((const ModConstF*)args.mc)[m_idx];
@@ -673,7 +684,7 @@ __global__ __launch_bounds__(NTT_THREADS) __attribute__((amdgpu_waves_per_eu(3, 
     load_tw<A, 2>(P.tw, 512 * TA + 2 * tid, wd);
     load_tw<A, 2>(P.tw, 512 * TA + 2 * tid + 1, wd + 3);
     load_tw<A, 3>(P.tw, 64 * TA + 8 * d3 + d2, wc);
-    const size_t moff = ((size_t)pl.spos[tile.a] << args.log_n) + off + 8 * tid;  // MUL: the multiplier's point
+    const size_t moff = ((size_t)pl_at(pl.spos, tile.a) << args.log_n) + off + 8 * tid;  // MUL: the multiplier's point
     {
         const ulonglong2* in = reinterpret_cast<const ulonglong2*>(P.src + off + 8 * tid);
 #pragma unroll
@@ -853,7 +864,7 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_hi_conv_kernel(NttArgs ar
 #pragma unroll
     for (int t = 0; t < T; t++) {
         const u32 a_idx = a0 + t < pl.n ? a0 + t : pl.n - 1;  // a ragged last group repeats its last limb and skips the store
-        P[t] = poly_ref<A>(args, pl, b, a_idx);
+        P[t] = poly_ref<A, true>(args, pl, b, a_idx);
         const TwF* ce = cp.convf + (size_t)pl.dpos[a_idx] * AP;
 #pragma unroll
         for (int a = 0; a < AP; a++) cw[t][a] = ce[a];
@@ -938,7 +949,7 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_inv_hi_kernel(NttArgs args, P
     const u32 tid = threadIdx.x;
     const PolyRef<A> P = poly_ref<A>(args, pl, blockIdx.y / pl.n, blockIdx.y % pl.n);
     u64* dst = P.dst + (size_t)blockIdx.x * CC;  // the lo pass has already moved the data to dst
-    const TwF* scale = args.inv_scale ? args.inv_scale + pl.mod[blockIdx.y % pl.n] : nullptr;
+    const TwF* scale = args.inv_scale ? args.inv_scale + pl_at(pl.mod, blockIdx.y % pl.n) : nullptr;
     E v[8];
     if constexpr (LOG_HI <= 3) {
         constexpr int KC = 8 / R;
