@@ -318,7 +318,7 @@ int run_ctct(const ckks_ctx* c, u32 level, const u64* const* a, size_t a_cstride
             keys[i] = d_rlk;
             vs[i] = ws.v + i * ws.v_b;
         }
-        HIP_TRY(launch_ntt_lo_mac(c, level, dsrc(c, ws, 0), keys, nullptr, nullptr, vs, n, st));
+        HIP_TRY(launch_ntt_lo_mac(c, level, dsrc(c, ws, 0), keys, vs, n, st));
     } else {
         HIP_TRY(launch_key_inner_multi(c, level, dsrc(c, ws, 0), d_rlk, 1, ws.v, ws.v_b, n, st));
     }
@@ -349,6 +349,7 @@ int run_ctct_merged(const ckks_ctx* c, u32 level, const u64* const* a, size_t a_
     if (!carve_ks(c, level, n, n, ar, ws)) return set_err(c, CKKS_ERR_WORKSPACE_TOO_SMALL, "workspace too small for ct-ct multiply");
     const bool mac = ntt_has_modup(c);  // the inner product inside the forward transforms' second pass
     if (lin && (!mac || addend)) return set_err(c, CKKS_ERR_INVALID_ARG, "internal: linear addend without the fused inner product");
+    if (mac && addend) return set_err(c, CKKS_ERR_INVALID_ARG, "internal: with the fused inner product the addend is given as a linear combination");
     const u64 *d2s[CT_BATCH], *add0[CT_BATCH], *add1[CT_BATCH];
     u64* vs[CT_BATCH];
     FinalItem items[CT_BATCH];
@@ -359,8 +360,6 @@ int run_ctct_merged(const ckks_ctx* c, u32 level, const u64* const* a, size_t a_
         for (u32 i = 0; i < n; i++) {
             a1[i] = a[i] + a_cstride;
             b1[i] = b[i] + b_cstride;
-            add0[i] = addend ? addend + i * add_bstride : nullptr;
-            add1[i] = addend ? addend + i * add_bstride + L1 * N : nullptr;
             vs[i] = ws.v + i * ws.v_b;
             keys[i] = d_rlk;
             items[i] = FinalItem{nullptr, nullptr, nullptr, outs[i], 1, 0};
@@ -376,7 +375,7 @@ int run_ctct_merged(const ckks_ctx* c, u32 level, const u64* const* a, size_t a_
             prod.y_cstride = lin->y_cstride;
             prod.kb = lin->kb;
         }
-        HIP_TRY(launch_ntt_lo_mac(c, level, dsrc(c, ws, 0), keys, addend ? add0 : nullptr, addend ? add1 : nullptr, vs, n, st, &prod));
+        HIP_TRY(launch_ntt_lo_mac(c, level, dsrc(c, ws, 0), keys, vs, n, st, &prod));
         return run_moddown(c, level, ws, n, items, st, true);
     }
     HIP_TRY(launch_tensor(c, level, ptr_list(a, n), a_cstride, ptr_list(b, n), b_cstride, d0, d1, d2, n, addend, add_bstride, st));
@@ -982,7 +981,7 @@ int ckks_keyswitch(const ckks_ctx* c, const uint64_t* d_c, uint32_t level, const
     if (rc) return rc;
     if (mac) {
         const u64* k = key->d_key;
-        HIP_TRY(launch_ntt_lo_mac(c, level, dsrc(c, ws, 0), &k, nullptr, nullptr, &ws.v, 1, st));
+        HIP_TRY(launch_ntt_lo_mac(c, level, dsrc(c, ws, 0), &k, &ws.v, 1, st));
     } else {
         HIP_TRY(launch_key_inner(c, level, dsrc(c, ws, 0), key->d_key, 1, ws.v, st));
     }
@@ -1081,7 +1080,7 @@ int ckks_rotate_hoisted(const ckks_ctx* c, const uint64_t* d_ct, uint32_t level,
                 ks[b] = pend_key[b]->d_key;
                 vs[b] = ws.v + b * ws.v_b;
             }
-            HIP_TRY(launch_ntt_lo_mac(c, level, dsrc(c, ws, 0), ks, nullptr, nullptr, vs, nb, st));
+            HIP_TRY(launch_ntt_lo_mac(c, level, dsrc(c, ws, 0), ks, vs, nb, st));
         } else {
             for (u32 b = 0; b < nb; b++) HIP_TRY(launch_key_inner(c, level, dsrc(c, ws, b), pend_key[b]->d_key, 1, ws.v + b * ws.v_b, st));
         }

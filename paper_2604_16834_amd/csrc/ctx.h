@@ -244,10 +244,10 @@ hipError_t launch_ntt_modup(const ckks_ctx* c, u32 level, u32 j, const double* y
                             const PolyList& pl, u32 batch, hipStream_t st, bool hi_only = false);
 // prod: the decomposed polynomial is the d2 = a1 (.) b1 of n ciphertext products and was never stored (the inverse
 // transform took it as a product, launch_ntt with mul_ptrs): the term of the digits' own limbs and the addends
-// d0 = a0 (.) b0 + add0, d1 = a0 (.) b1 + a1 (.) b0 + add1 are formed from the operands (host arrays of n device pointers,
+// d0 = a0 (.) b0, d1 = a0 (.) b1 + a1 (.) b0 are formed from the operands (host arrays of n device pointers,
 // [level+1][N] each).
 // lin (optional): the product's addend is the linear combination ka * x + kb * y of two more ciphertexts (component
-// strides x_cstride, y_cstride; ka, kb: one residue per q-limb), formed on the fly as well; add0s / add1s must then be null.
+// strides x_cstride, y_cstride; ka, kb: one residue per q-limb), formed on the fly as well.
 struct MacProduct {
     const u64* const* a0;
     const u64* const* a1;
@@ -259,8 +259,8 @@ struct MacProduct {
     const u64* ka = nullptr;
     const u64* kb = nullptr;
 };
-hipError_t launch_ntt_lo_mac(const ckks_ctx* c, u32 level, const DigitSrc& digits, const u64* const* keys, const u64* const* add0s,
-                             const u64* const* add1s, u64* const* outs, u32 n, hipStream_t st, const MacProduct* prod = nullptr);
+hipError_t launch_ntt_lo_mac(const ckks_ctx* c, u32 level, const DigitSrc& digits, const u64* const* keys, u64* const* outs, u32 n,
+                             hipStream_t st, const MacProduct* prod = nullptr);
 // whether launch_ntt can apply an epilogue in this ring (it needs the two-pass transform)
 inline bool ntt_has_epilogue(const ckks_ctx* c) { return c->log_n > CKKS_TILE_LOG; }
 // keyswitch.hip

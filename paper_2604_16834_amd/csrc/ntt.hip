@@ -458,19 +458,18 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_div_kernel(NttArgs arg
 // slice of every digit whose limb e went through the converting hi pass (all live digits but the one e belongs to; the
 // slice's twiddles are fetched once for all of them), multiplies each result by the two key words of (digit, e) as it
 // comes out, adds the product of the digit that owns e (its limb is the decomposed polynomial's own, never transformed)
-// and, on the q-limbs, P times the optional addends, and stores the two components of the inner product: the extended
+// and stores the two components of the inner product: the extended
 // digits are never written in evaluation form nor read back.  All sums are exact integers in doubles (at most
 // beta + 1 terms below 0.75 q each).
 struct MacEpilogue {
     DigitSrc D;           // D.digits: rows (j*E + e) hold the hi pass' output (doubles); D.own: the decomposed polynomials
     PtrList8 key;         // per batch item: [dnum][2][M][N] (the same pointer for a shared key)
-    PtrList8 add0, add1;  // per batch item, optional: [level+1][N]
     OutList8 out;         // per batch item: [2][E][N]
     const u64* negp;      // [num_q]: -P mod q_i
     u32 level, M, E, beta;
     // prod != 0: the decomposed polynomial is d2 = a1 (.) b1 of the ciphertext product (a0, a1) x (b0, b1), which exists
     // nowhere in evaluation form: the own-limb term is formed from a1, b1 ([level+1][N] each, per batch item), and the
-    // addends are d0 = a0 (.) b0 + add0 and d1 = a0 (.) b1 + a1 (.) b0 + add1 (D.own is not read)
+    // addends are d0 = a0 (.) b0 and d1 = a0 (.) b1 + a1 (.) b0 (D.own is not read)
     PtrList8 a0, a1, b0, b1;
     u32 prod, lin;
     // lin != 0 (with prod): the addends are ka * x + kb * y of two more ciphertexts (component 1 at + x_cstride, y_cstride)
@@ -479,10 +478,10 @@ struct MacEpilogue {
     u64 ka[CKKS_MAX_MODULI], kb[CKKS_MAX_MODULI];
 };
 
-// PROD, LIN: ep.prod, ep.lin.  ADD: 0 = no addends, 1 = every batch item has both, 2 = look at the pointers.  They are
-// template arguments so that what follows the digits is straight-line code: with the operands behind conditions, even ones that
-// are the same for the whole launch, the compiler keeps each request next to its use, one round trip to memory per point.
-template <bool PROD, int ADD, bool LIN>
+// PROD, LIN: ep.prod, ep.lin.  They are template arguments so that what follows the digits is straight-line code: with the
+// operands behind conditions, even ones that are the same for the whole launch, the compiler keeps each request next to its
+// use, one round trip to memory per point.
+template <bool PROD, bool LIN>
 __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_mac_kernel(NttArgs args, PolyList pl, MacEpilogue ep) {
     typedef ArithF64 A;
     typedef double E;
@@ -576,37 +575,26 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_mac_kernel(NttArgs arg
         const u64* kj = key + (size_t)own * 2 * kstride;
         const size_t po = (size_t)e * N + off;
         const u64 *pa0 = ep.a0.p[b] + po, *pa1 = ep.a1.p[b] + po, *pb0 = ep.b0.p[b] + po, *pb1 = ep.b1.p[b] + po;
-        const u64* c0 = ADD ? ep.add0.p[b] : nullptr;
-        const u64* c1 = ADD ? ep.add1.p[b] : nullptr;
         const double pres = mc.q - A::from_u64(ep.negp[e]);  // P mod q_e
         const u64* lx = LIN ? ep.lx.p[b] + po : nullptr;
         const u64* ly = LIN ? ep.ly.p[b] + po : nullptr;
         const double ka = LIN ? A::from_u64(ep.ka[e]) : 0.0, kb = LIN ? A::from_u64(ep.kb[e]) : 0.0;
 #pragma unroll
         for (int h = 0; h < 8; h += 4) {  // four points at a time: up to ten operands per point, requested before the first is used
-            u64 ra0[4], ra1[4], rb0[4], rb1[4], rk0[4], rk1[4], rc0[4], rc1[4], rx0[4], rx1[4], ry0[4], ry1[4];
+            u64 ra0[4], ra1[4], rb0[4], rb1[4], rk0[4], rk1[4], rx0[4], rx1[4], ry0[4], ry1[4];
 #pragma unroll
             for (int i = 0; i < 4; i++) {
                 const u32 x = tid + 256 * (h + i);
                 ra0[i] = pa0[x], ra1[i] = pa1[x], rb0[i] = pb0[x], rb1[i] = pb1[x];
                 rk0[i] = kj[x], rk1[i] = kj[kstride + x];
-                if (ADD == 1) rc0[i] = c0[po + x], rc1[i] = c1[po + x];
                 if (LIN) rx0[i] = lx[x], rx1[i] = lx[ep.x_cstride + x], ry0[i] = ly[x], ry1[i] = ly[ep.y_cstride + x];
             }
 #pragma unroll
             for (int i = 0; i < 4; i++) {
-                const u32 x = tid + 256 * (h + i);
                 const double A0 = A::from_u64(ra0[i]), A1 = A::from_u64(ra1[i]), B0 = A::from_u64(rb0[i]), B1 = A::from_u64(rb1[i]);
                 const double dd2 = A::mulmod_any(A1, B1, mc.q, mc.qinv);
                 double dd0 = A::mulmod_any(A0, B0, mc.q, mc.qinv);
                 double dd1 = A::mulmod_any(A0, B1, mc.q, mc.qinv) + A::mulmod_any(A1, B0, mc.q, mc.qinv);
-                if (ADD == 1) {
-                    dd0 += A::from_u64(rc0[i]);
-                    dd1 += A::from_u64(rc1[i]);
-                } else if (ADD == 2) {
-                    if (c0) dd0 += A::from_u64(c0[po + x]);
-                    if (c1) dd1 += A::from_u64(c1[po + x]);
-                }
                 if (LIN) {  // at most 0.75 q more per term: both sums stay below 2^53
                     dd0 += A::mulmod_any(A::from_u64(rx0[i]), ka, mc.q, mc.qinv) + A::mulmod_any(A::from_u64(ry0[i]), kb, mc.q, mc.qinv);
                     dd1 += A::mulmod_any(A::from_u64(rx1[i]), ka, mc.q, mc.qinv) + A::mulmod_any(A::from_u64(ry1[i]), kb, mc.q, mc.qinv);
@@ -618,39 +606,20 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_mac_kernel(NttArgs arg
             }
         }
     } else if (!PROD && e <= ep.level) {
-        // the digit that owns this limb, and P times the optional addends
+        // the digit that owns this limb
         const u64* kj = key + (size_t)own * 2 * kstride;
         const u64* yo = ep.D.own.p[b] + (size_t)e * N + off;
-        const double pres = mc.q - A::from_u64(ep.negp[e]);  // P mod q_e
-        const u64* a0 = ADD ? ep.add0.p[b] : nullptr;
-        const u64* a1 = ADD ? ep.add1.p[b] : nullptr;
-        const size_t po = (size_t)e * N + off;
-        u64 ry[8], rk0[8], rk1[8], r0[8], r1[8];
+        u64 ry[8], rk0[8], rk1[8];
 #pragma unroll
         for (int i = 0; i < 8; i++) {
             const u32 x = tid + 256 * i;
             ry[i] = yo[x], rk0[i] = kj[x], rk1[i] = kj[kstride + x];
-            if (ADD == 1) r0[i] = a0[po + x], r1[i] = a1[po + x];
         }
 #pragma unroll
         for (int i = 0; i < 8; i++) {
             const double y = A::from_u64(ry[i]);
             acc0[i] += A::mulmod_any(y, A::from_u64(rk0[i]), mc.q, mc.qinv);
             acc1[i] += A::mulmod_any(y, A::from_u64(rk1[i]), mc.q, mc.qinv);
-            if (ADD == 1) {
-                acc0[i] += A::mulmod_any(A::from_u64(r0[i]), pres, mc.q, mc.qinv);
-                acc1[i] += A::mulmod_any(A::from_u64(r1[i]), pres, mc.q, mc.qinv);
-            }
-        }
-        if (ADD == 2) {
-            if (a0) {
-#pragma unroll
-                for (int i = 0; i < 8; i++) acc0[i] += A::mulmod_any(A::from_u64(a0[po + tid + 256 * i]), pres, mc.q, mc.qinv);
-            }
-            if (a1) {
-#pragma unroll
-                for (int i = 0; i < 8; i++) acc1[i] += A::mulmod_any(A::from_u64(a1[po + tid + 256 * i]), pres, mc.q, mc.qinv);
-            }
         }
     }
     u64* o0 = ep.out.p[b] + (size_t)e * N + off;
@@ -1237,8 +1206,8 @@ hipError_t launch_ntt_rescale(const ckks_ctx* c, u32 level, const double* y, u64
     return launch_ntt_any(c, false, dst, level, dst, level, pl, batch, st, nullptr, epilogue, nullptr, &cp);
 }
 
-hipError_t launch_ntt_lo_mac(const ckks_ctx* c, u32 level, const DigitSrc& digits, const u64* const* keys, const u64* const* add0s,
-                             const u64* const* add1s, u64* const* outs, u32 n, hipStream_t st, const MacProduct* prod) {
+hipError_t launch_ntt_lo_mac(const ckks_ctx* c, u32 level, const DigitSrc& digits, const u64* const* keys, u64* const* outs, u32 n,
+                             hipStream_t st, const MacProduct* prod) {
     if (!ntt_has_modup(c) || c->log_hi == 0 || n == 0 || n > KS_MAX_BATCH) return hipErrorInvalidValue;
     const u32 E = c->ext_limbs(level), beta = c->live_digits(level);
     NttArgs args = {};
@@ -1260,8 +1229,6 @@ hipError_t launch_ntt_lo_mac(const ckks_ctx* c, u32 level, const DigitSrc& digit
     double n_add = 0.0, n_keys = 0.0;
     for (u32 b = 0; b < KS_MAX_BATCH; b++) {
         ep.key.p[b] = b < n ? keys[b] : nullptr;
-        ep.add0.p[b] = (b < n && add0s) ? add0s[b] : nullptr;
-        ep.add1.p[b] = (b < n && add1s) ? add1s[b] : nullptr;
         ep.out.p[b] = b < n ? outs[b] : nullptr;
         if (b < n && !ep.key.p[b]) return hipErrorInvalidValue;
         ep.a0.p[b] = (prod && b < n) ? prod->a0[b] : nullptr;
@@ -1269,7 +1236,6 @@ hipError_t launch_ntt_lo_mac(const ckks_ctx* c, u32 level, const DigitSrc& digit
         ep.b0.p[b] = (prod && b < n) ? prod->b0[b] : nullptr;
         ep.b1.p[b] = (prod && b < n) ? prod->b1[b] : nullptr;
         if (prod && b < n && (!ep.a0.p[b] || !ep.a1.p[b] || !ep.b0.p[b] || !ep.b1.p[b])) return hipErrorInvalidValue;
-        n_add += (ep.add0.p[b] ? 1.0 : 0.0) + (ep.add1.p[b] ? 1.0 : 0.0);
         if (b < n && (b == 0 || keys[b] != keys[b - 1])) n_keys += 1.0;
     }
     ep.negp = c->d_moddown + 2 * c->k_pad + (size_t)c->k_pad * c->num_q + 2 * c->num_q;
@@ -1279,7 +1245,7 @@ hipError_t launch_ntt_lo_mac(const ckks_ctx* c, u32 level, const DigitSrc& digit
     ep.beta = beta;
     ep.prod = prod ? 1 : 0;
     ep.lin = (prod && prod->lin_x) ? 1 : 0;
-    if (ep.lin && (add0s || add1s || !prod->lin_y || !prod->ka || !prod->kb)) return hipErrorInvalidValue;
+    if (ep.lin && (!prod->lin_y || !prod->ka || !prod->kb)) return hipErrorInvalidValue;
     ep.x_cstride = ep.lin ? prod->x_cstride : 0;
     ep.y_cstride = ep.lin ? prod->y_cstride : 0;
     for (u32 b = 0; b < KS_MAX_BATCH; b++) {
@@ -1299,20 +1265,10 @@ hipError_t launch_ntt_lo_mac(const ckks_ctx* c, u32 level, const DigitSrc& digit
     ProfScope ps__(c, K_NTT_FWD_LO, st, 8.0 * c->N * (n * (n_tr + (prod ? 4.0 : 1.0) * (level + 1.0) + 2.0 * E) + n_add * (level + 1.0) + n_keys * 2.0 * beta * E),
                    0.5 * n * n_tr * c->N * c->log_lo);
     // which operands join after the digits is the same for the whole launch: one instantiation per case
-    u32 with0 = 0, with1 = 0;
-    for (u32 b = 0; b < n; b++) with0 += ep.add0.p[b] ? 1 : 0, with1 += ep.add1.p[b] ? 1 : 0;
-    const int addm = (with0 == 0 && with1 == 0) ? 0 : ((with0 == n && with1 == n) ? 1 : 2);
-#define LO_MAC_LAUNCH(PROD, ADD, LIN) hipLaunchKernelGGL((ntt_fwd_lo_mac_kernel<PROD, ADD, LIN>), grid, dim3(NTT_THREADS), 0, st, args, pl, ep)
-    if (ep.lin) LO_MAC_LAUNCH(true, 0, true);  // the linear combination excludes addends (checked above)
-    else if (ep.prod) {
-        if (addm == 0) LO_MAC_LAUNCH(true, 0, false);
-        else if (addm == 1) LO_MAC_LAUNCH(true, 1, false);
-        else LO_MAC_LAUNCH(true, 2, false);
-    } else {
-        if (addm == 0) LO_MAC_LAUNCH(false, 0, false);
-        else if (addm == 1) LO_MAC_LAUNCH(false, 1, false);
-        else LO_MAC_LAUNCH(false, 2, false);
-    }
+#define LO_MAC_LAUNCH(PROD, LIN) hipLaunchKernelGGL((ntt_fwd_lo_mac_kernel<PROD, LIN>), grid, dim3(NTT_THREADS), 0, st, args, pl, ep)
+    if (ep.lin) LO_MAC_LAUNCH(true, true);
+    else if (ep.prod) LO_MAC_LAUNCH(true, false);
+    else LO_MAC_LAUNCH(false, false);
 #undef LO_MAC_LAUNCH
     return hipGetLastError();
 }
