@@ -489,32 +489,39 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_mac_kernel(NttArgs arg
     __shared__ E lds1[LDS_PADDED_WORDS];
     const u32 tid = threadIdx.x;
     const LoTile tile = lo_tile(args.log_hi, args.lo_group);
-    const u32 blk = tile.blk, b = tile.b, e = tile.a, m_idx = pl_at(pl.mod, e);
+    const u32 blk = tile.blk, e = tile.a, m_idx = pl_at(pl.mod, e);
+    // the batch items of this workgroup: tile.b, tile.b + (the grid's extent over items), ...: a workgroup that takes several
+    // fetches the slice's twiddles (as many bytes as an item's points) once for all of them and requests an item's first
+    // points before it is done with the previous item
+    const u32 b_step = args.lo_group ? gridDim.y : gridDim.x;
     const size_t N = (size_t)1 << args.log_n, off = (size_t)blk << 11;
     const TwF* tw = (const TwF*)args.tw + ((size_t)m_idx << args.log_n);
     const ModConstF mc = ((const ModConstF*)args.mc)[m_idx];
     const u32 own = e <= ep.level ? e / ep.D.alpha : 0xffffffffu;  // the digit that limb e belongs to
     const u32 TA = (1u << args.log_hi) + blk;
     const u32 d3 = tid >> 5, x5 = tid & 31, d2 = (tid >> 2) & 7, d0 = tid & 3;
-    const u64* key = ep.key.p[b] + (size_t)m_idx * N + off;
     const size_t kstride = (size_t)ep.M * N;  // between the b and the a part of a digit's key; two of them per digit
-    const double* hi = (const double*)(ep.D.digits + b * ep.D.bstride) + (size_t)e * N + off;
     const size_t dstride = (size_t)ep.E * N;
-    E acc0[8], acc1[8];
-#pragma unroll
-    for (int j = 0; j < 8; j++) acc0[j] = acc1[j] = 0.0;
-    TwF wa[7], wb[7], wc[7], wd[6];  // the slice's twiddles, fetched once for all digits
+    TwF wa[7], wb[7], wc[7], wd[6];  // the slice's twiddles, fetched once for all digits of all items
     load_tw<A, 3>(tw, TA, wa);
     load_tw<A, 3>(tw, 8 * TA + d3, wb);
     load_tw<A, 3>(tw, 64 * TA + 8 * d3 + d2, wc);
     load_tw<A, 2>(tw, 512 * TA + 2 * tid, wd);
     load_tw<A, 2>(tw, 512 * TA + 2 * tid + 1, wd + 3);
-    u32 j = own == 0 ? 1 : 0;  // first digit to transform
+    const u32 j0 = own == 0 ? 1 : 0;  // first digit to transform
     E v[8], raw[8];
-    if (j < ep.beta) {
+    if (j0 < ep.beta) {
+        const double* hi0 = (const double*)(ep.D.digits + tile.b * ep.D.bstride) + (size_t)e * N + off;
 #pragma unroll
-        for (int i = 0; i < 8; i++) raw[i] = hi[(size_t)j * dstride + tid + 256 * i];
+        for (int i = 0; i < 8; i++) raw[i] = hi0[(size_t)j0 * dstride + tid + 256 * i];
     }
+    for (u32 b = tile.b; b < args.batch; b += b_step) {
+    const u64* key = ep.key.p[b] + (size_t)m_idx * N + off;
+    const double* hi = (const double*)(ep.D.digits + b * ep.D.bstride) + (size_t)e * N + off;
+    E acc0[8], acc1[8];
+#pragma unroll
+    for (int j = 0; j < 8; j++) acc0[j] = acc1[j] = 0.0;
+    u32 j = j0;
     while (j < ep.beta) {
         u32 jn = j + 1;
         if (jn == own) jn++;
@@ -570,6 +577,16 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_mac_kernel(NttArgs arg
         }
         j = jn;
     }
+    // the next item's first points: requested before the operands of what follows, or, where those leave no registers (the
+    // linear combination's twelve operands per point), after them
+    auto request_next = [&]() {
+        if (b + b_step < args.batch && j0 < ep.beta) {
+            const double* hin = (const double*)(ep.D.digits + (b + b_step) * ep.D.bstride) + (size_t)e * N + off;
+#pragma unroll
+            for (int i = 0; i < 8; i++) raw[i] = hin[(size_t)j0 * dstride + tid + 256 * i];
+        }
+    };
+    if (!LIN) request_next();
     if (PROD && e <= ep.level) {
         // the tensor product of this slice, formed here: d2 feeds the digit that owns the limb, P d0 and P d1 join the sums
         const u64* kj = key + (size_t)own * 2 * kstride;
@@ -579,18 +596,21 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_mac_kernel(NttArgs arg
         const u64* lx = LIN ? ep.lx.p[b] + po : nullptr;
         const u64* ly = LIN ? ep.ly.p[b] + po : nullptr;
         const double ka = LIN ? A::from_u64(ep.ka[e]) : 0.0, kb = LIN ? A::from_u64(ep.kb[e]) : 0.0;
+        // four points at a time (two with the linear combination: the twiddles stay in registers for the next item and leave
+        // room for 24 operands): six to ten operands per point, requested before the first is used
+        constexpr int HP = LIN ? 2 : 4;
 #pragma unroll
-        for (int h = 0; h < 8; h += 4) {  // four points at a time: up to ten operands per point, requested before the first is used
-            u64 ra0[4], ra1[4], rb0[4], rb1[4], rk0[4], rk1[4], rx0[4], rx1[4], ry0[4], ry1[4];
+        for (int h = 0; h < 8; h += HP) {
+            u64 ra0[HP], ra1[HP], rb0[HP], rb1[HP], rk0[HP], rk1[HP], rx0[HP], rx1[HP], ry0[HP], ry1[HP];
 #pragma unroll
-            for (int i = 0; i < 4; i++) {
+            for (int i = 0; i < HP; i++) {
                 const u32 x = tid + 256 * (h + i);
                 ra0[i] = pa0[x], ra1[i] = pa1[x], rb0[i] = pb0[x], rb1[i] = pb1[x];
                 rk0[i] = kj[x], rk1[i] = kj[kstride + x];
                 if (LIN) rx0[i] = lx[x], rx1[i] = lx[ep.x_cstride + x], ry0[i] = ly[x], ry1[i] = ly[ep.y_cstride + x];
             }
 #pragma unroll
-            for (int i = 0; i < 4; i++) {
+            for (int i = 0; i < HP; i++) {
                 const double A0 = A::from_u64(ra0[i]), A1 = A::from_u64(ra1[i]), B0 = A::from_u64(rb0[i]), B1 = A::from_u64(rb1[i]);
                 const double dd2 = A::mulmod_any(A1, B1, mc.q, mc.qinv);
                 double dd0 = A::mulmod_any(A0, B0, mc.q, mc.qinv);
@@ -622,12 +642,16 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_mac_kernel(NttArgs arg
             acc1[i] += A::mulmod_any(y, A::from_u64(rk1[i]), mc.q, mc.qinv);
         }
     }
+    if (LIN) request_next();
     u64* o0 = ep.out.p[b] + (size_t)e * N + off;
     u64* o1 = o0 + (size_t)ep.E * N;
 #pragma unroll
     for (int i = 0; i < 8; i++) {
         o0[tid + 256 * i] = A::canonical(A::reduce(acc0[i], mc), mc);
         o1[tid + 256 * i] = A::canonical(A::reduce(acc1[i], mc), mc);
+    }
+    // (no barrier between items: the next item's first exchange writes lds0, and its barrier stands between the last item's
+    // reads of lds1 and the next writes to it)
     }
 }
 
@@ -1259,7 +1283,11 @@ hipError_t launch_ntt_lo_mac(const ckks_ctx* c, u32 level, const DigitSrc& digit
     }
     // digits transformed per batch item: every (digit, position) pair but the digits' own limbs
     const double n_tr = (double)beta * E - (level + 1.0);
-    const dim3 grid = args.lo_group ? dim3(args.lo_group, n, slices / args.lo_group) : dim3(n, slices);
+    // the grid's extent over the batch: two, i.e. four items per workgroup in a batch of eight (measured: 16.5 ms per step for
+    // the lo-pass class with one item per workgroup, 16.35 with all eight, 16.15 with four, which still leave the chip's 256
+    // CUs, two workgroups each, four rounds of workgroups)
+    const u32 b_ext = n < 2 ? n : 2;
+    const dim3 grid = args.lo_group ? dim3(args.lo_group, b_ext, slices / args.lo_group) : dim3(b_ext, slices);
     // in: the transformed rows, the own limbs, the addends, the keys (once per distinct key); out: two components
     if (ep.lin) n_add = 4.0 * n;  // two components of two ciphertexts
     ProfScope ps__(c, K_NTT_FWD_LO, st, 8.0 * c->N * (n * (n_tr + (prod ? 4.0 : 1.0) * (level + 1.0) + 2.0 * E) + n_add * (level + 1.0) + n_keys * 2.0 * beta * E),
