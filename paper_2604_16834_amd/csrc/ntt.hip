@@ -441,10 +441,85 @@ __device__ __forceinline__ void fwd_lo_body(const NttArgs& args, const PolyList&
     }
 }
 
-template <class A, int IT>
-__global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_kernel(NttArgs args, PolyList pl) {
-    FwdEpilogue none;  // never read
-    fwd_lo_body<A, IT, false>(args, pl, none);
+// The plain forward lo pass with the workgroup's batch items in a loop: items tile.b, tile.b + (the grid's extent over
+// items), ... of the same 2^11-point slice.  The slice's 27 twiddle words per thread are 432 bytes against the 128 bytes of
+// an item's points and results, so a workgroup that fetches them for two items still moves more twiddles than data through
+// the CU's cache; this one fetches them once for all its items and requests an item's points while the previous one is
+// transformed.  Same rounds, same LDS exchanges as fwd_lo_body.
+template <class A>
+__global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_loop_kernel(NttArgs args, PolyList pl) {
+    typedef typename A::E E;
+    typedef typename A::TW TW;
+    __shared__ E lds0[LDS_PADDED_WORDS];
+    __shared__ E lds1[LDS_PADDED_WORDS];
+    const u32 tid = threadIdx.x;
+    const LoTile tile = lo_tile(args.log_hi, args.lo_group);
+    const u32 b_step = args.lo_group ? gridDim.y : gridDim.x;
+    const u32 blk = tile.blk;
+    const PolyRef<A> P = poly_ref<A>(args, pl, tile.b, tile.a);
+    const size_t off = (size_t)blk << 11;
+    const u32 TA = (1u << args.log_hi) + blk;
+    const u32 d3 = tid >> 5, x5 = tid & 31, d2 = (tid >> 2) & 7, d0 = tid & 3;
+    E v[8];
+    u64 raw[8];
+    TW wa[7], wb[7], wc[7], wd[6];
+    load_tw<A, 3>(P.tw, TA, wa);
+    {
+        const u64* src = P.src + off;
+#pragma unroll
+        for (int j = 0; j < 8; j++) raw[j] = src[tid + 256 * j];
+    }
+    load_tw<A, 3>(P.tw, 8 * TA + d3, wb);
+    load_tw<A, 3>(P.tw, 64 * TA + 8 * d3 + d2, wc);
+    load_tw<A, 2>(P.tw, 512 * TA + 2 * tid, wd);
+    load_tw<A, 2>(P.tw, 512 * TA + 2 * tid + 1, wd + 3);
+    for (u32 b = tile.b; b < args.batch; b += b_step) {
+        if (args.first) {
+#pragma unroll
+            for (int j = 0; j < 8; j++) v[j] = A::load_first(raw[j], P.mc, false);
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; j++) v[j] = A::load_mid(raw[j]);
+        }
+        if (b + b_step < args.batch) {  // the next item's points, a tile ahead
+            const u64* src = item_src<A>(args, pl, b + b_step, tile.a) + off;
+#pragma unroll
+            for (int j = 0; j < 8; j++) raw[j] = src[tid + 256 * j];
+        }
+        fwd_rows_pre<A, 3>(v, wa, P.mc);
+        A::fwd_round_end(v, P.mc);
+#pragma unroll
+        for (int j = 0; j < 8; j++) lds0[LDS_PAD(tid + 256 * j)] = v[j];
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 8; j++) v[j] = lds0[LDS_PAD(d3 * 256 + 32 * j + x5)];
+        fwd_rows_pre<A, 3>(v, wb, P.mc);
+        A::fwd_round_end(v, P.mc);
+#pragma unroll
+        for (int j = 0; j < 8; j++) lds1[LDS_PAD(d3 * 256 + 32 * j + x5)] = v[j];
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 8; j++) v[j] = lds1[LDS_PAD(d3 * 256 + d2 * 32 + 4 * j + d0)];
+        fwd_rows_pre<A, 3>(v, wc, P.mc);
+        A::fwd_round_end(v, P.mc);
+#pragma unroll
+        for (int j = 0; j < 8; j++) lds0[LDS_PAD(d3 * 256 + d2 * 32 + 4 * j + d0)] = v[j];
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 8; j++) v[j] = lds0[LDS_PAD(8 * tid + j)];
+        fwd_rows_pre<A, 2>(v, wd, P.mc);
+        fwd_rows_pre<A, 2>(v + 4, wd + 3, P.mc);
+        A::fwd_round_end(v, P.mc);
+        // back through LDS so that a wave stores 512 contiguous bytes per instruction
+#pragma unroll
+        for (int j = 0; j < 8; j++) lds1[LDS_PAD(8 * tid + j)] = v[j];
+        __syncthreads();
+        u64* dst = item_dst(args, pl, b, tile.a) + off;
+#pragma unroll
+        for (int j = 0; j < 8; j++) dst[tid + 256 * j] = A::store_fwd_final(lds1[LDS_PAD(tid + 256 * j)], P.mc);
+        // (no barrier between items: the next item's first exchange writes lds0, whose last read is behind the barrier above,
+        // and its first barrier stands between these reads of lds1 and the next writes to it)
+    }
 }
 
 // the lo pass as the last kernel of a division by dropped moduli
@@ -1023,15 +1098,26 @@ static void launch_hi_any(u32 log_hi, bool inverse, dim3 grid, hipStream_t st, c
 }
 
 template <class A, int IT>
-static void launch_lo_it(bool inverse, dim3 grid, hipStream_t st, const NttArgs& args, const PolyList& pl, bool mul = false) {
+static void launch_inv_lo_it(dim3 grid, hipStream_t st, const NttArgs& args, const PolyList& pl, bool mul = false) {
     if constexpr (std::is_same<A, ArithF64>::value) {
-        if (inverse && mul) {
+        if (mul) {
             hipLaunchKernelGGL((ntt_inv_lo_kernel<A, IT, true>), grid, dim3(NTT_THREADS), 0, st, args, pl);
             return;
         }
     }
-    if (inverse) hipLaunchKernelGGL((ntt_inv_lo_kernel<A, IT>), grid, dim3(NTT_THREADS), 0, st, args, pl);
-    else hipLaunchKernelGGL((ntt_fwd_lo_kernel<A, IT>), grid, dim3(NTT_THREADS), 0, st, args, pl);
+    hipLaunchKernelGGL((ntt_inv_lo_kernel<A, IT>), grid, dim3(NTT_THREADS), 0, st, args, pl);
+}
+// The plain forward lo pass: workgroups that loop over their items, up to eight each (measured at N = 2^16: 2, 4, 8 and 16
+// items give 2.04, 2.06, 2.08 and 2.10e6 limb transforms per second against 1.97e6 with one fetch of the twiddles per two
+// items; eight still leaves the layer's batches of eight a grid of one workgroup per slice).  `grid` is a lo pass' grid,
+// whose extent over items is set here.
+template <class A>
+static void launch_fwd_lo_loop(u32 batch, dim3 grid, hipStream_t st, const NttArgs& args, const PolyList& pl) {
+    constexpr u32 per_wg = 8;
+    const u32 ext = (batch + per_wg - 1) / per_wg;
+    if (args.lo_group) grid.y = ext;
+    else grid.x = ext;
+    hipLaunchKernelGGL((ntt_fwd_lo_loop_kernel<A>), grid, dim3(NTT_THREADS), 0, st, args, pl);
 }
 template <class A>
 static void launch_lo_div(u32 items, dim3 grid, hipStream_t st, const NttArgs& args, const PolyList& pl, const FwdEpilogue& ep) {
@@ -1057,9 +1143,9 @@ static void launch_lo_div(u32 items, dim3 grid, hipStream_t st, const NttArgs& a
 #undef LO_DIV_LAUNCH
 }
 template <class A>
-static void launch_lo(bool inverse, u32 items, dim3 grid, hipStream_t st, const NttArgs& args, const PolyList& pl, bool mul = false) {
-    if (items == 2) launch_lo_it<A, 2>(inverse, grid, st, args, pl, mul);
-    else launch_lo_it<A, 1>(inverse, grid, st, args, pl, mul);
+static void launch_inv_lo(u32 items, dim3 grid, hipStream_t st, const NttArgs& args, const PolyList& pl, bool mul = false) {
+    if (items == 2) launch_inv_lo_it<A, 2>(grid, st, args, pl, mul);
+    else launch_inv_lo_it<A, 1>(grid, st, args, pl, mul);
 }
 
 constexpr u32 CONV_TARGETS = 4;  // target limbs per workgroup of the converting hi pass
@@ -1141,9 +1227,11 @@ static hipError_t launch_ntt_any(const ckks_ctx* c, bool inverse, const u64* src
     }
     const dim3 grid(c->N >> CKKS_TILE_LOG, polys);  // hi pass: one workgroup per 2^11 points
     const u32 slices = pl.n << c->log_hi;
-    // batch items per lo-pass workgroup: two share one fetch of the twiddles (four cost too many registers); the pass that
-    // ends a division takes one (with its epilogue's operands two items leave only two waves per SIMD, which costs more
-    // than the second fetch of the twiddles)
+    // batch items per lo-pass workgroup: in the inverse pass two share one fetch of the twiddles (an unrolled four cost too many
+    // registers, and a loop over the items as in the plain forward pass spills in the variant that forms a product as it
+    // loads, 4.7 -> 6.3 ms per step of the block slice); the pass that ends a division takes one (with its epilogue's operands
+    // two items leave only two waves per SIMD, which costs more than the second fetch of the twiddles); the plain forward
+    // pass sets its own extent (launch_fwd_lo_loop)
     const u32 lo_items = (batch >= 2 && !epilogue) ? 2 : 1;
     const u32 lo_wgs = (batch + lo_items - 1) / lo_items;
     const dim3 grid_lo = args.lo_group ? dim3(args.lo_group, lo_wgs, slices / args.lo_group) : dim3(lo_wgs, slices);  // see lo_tile()
@@ -1157,7 +1245,15 @@ static hipError_t launch_ntt_any(const ckks_ctx* c, bool inverse, const u64* src
     PolyList pd = pl;
     for (u32 i = 0; i < pl.n; i++) pd.spos[i] = pl.dpos[i];
     auto hi = [&](const NttArgs& a, const PolyList& l) { if (f64) launch_hi_any<ArithF64>(c->log_hi, inverse, grid, st, a, l); else launch_hi_any<ArithU64>(c->log_hi, inverse, grid, st, a, l); };
-    auto lo = [&](const NttArgs& a, const PolyList& l) { if (f64) launch_lo<ArithF64>(inverse, lo_items, grid_lo, st, a, l); else launch_lo<ArithU64>(inverse, lo_items, grid_lo, st, a, l); };
+    auto lo = [&](const NttArgs& a, const PolyList& l) {
+        if (!inverse) {
+            if (f64) launch_fwd_lo_loop<ArithF64>(batch, grid_lo, st, a, l);
+            else launch_fwd_lo_loop<ArithU64>(batch, grid_lo, st, a, l);
+        } else {
+            if (f64) launch_inv_lo<ArithF64>(lo_items, grid_lo, st, a, l);
+            else launch_inv_lo<ArithU64>(lo_items, grid_lo, st, a, l);
+        }
+    };
     if (!inverse) {
         if (c->log_hi > 0) {
             args.last = 0;
@@ -1185,7 +1281,7 @@ static hipError_t launch_ntt_any(const ckks_ctx* c, bool inverse, const u64* src
         args.last = c->log_hi == 0;
         {
             ProfScope ps__(c, K_NTT_INV_LO, st, mul_ptrs ? 1.5 * pass_bytes : pass_bytes, lo_ops);
-            if (mul_ptrs) launch_lo<ArithF64>(true, lo_items, grid_lo, st, args, pl, true);
+            if (mul_ptrs) launch_inv_lo<ArithF64>(lo_items, grid_lo, st, args, pl, true);
             else lo(args, pl);
         }
         if (c->log_hi > 0) { ProfScope ps__(c, K_NTT_INV_HI, st, pass_bytes, hi_ops); hi(second, pd); }
