@@ -41,6 +41,23 @@ def test_ntt_matches_oracle(log_n, bits):
     assert np.array_equal(hx.to_host(d), orc.ntt_many(polys, idx, inverse=True))
 
 
+@pytest.mark.parametrize("batch,bits", [(1, 50), (8, 50), (9, 50), (19, 50), (19, 57), (64, 50)])
+def test_ntt_batches_span_the_item_loop(batch, bits):
+    """The forward lo pass gives a workgroup up to eight polynomials of a batch, taken with the stride of the grid's extent
+    over items: batches of one item, of exactly eight, of one more, and of 19 and 64 (three and eight workgroups per slice, the
+    first with a ragged share) in both arithmetics; every residue against the oracle, forward and back."""
+    p = make_params(12, 2, 1, 1, bits=bits)
+    orc, ctx = both(p)
+    rng = np.random.default_rng(1000 + batch)
+    idx = [2, 0]
+    polys = np.stack([rand_poly(rng, [p.moduli[t] for t in idx], orc.N) for _ in range(batch)])
+    d = hx.from_host(polys)
+    hx.ckks_ntt_fwd(ctx, d, idx)
+    assert np.array_equal(hx.to_host(d), orc.ntt_many(polys, idx))
+    hx.ckks_ntt_inv(ctx, d, idx)
+    assert np.array_equal(hx.to_host(d), polys)
+
+
 def test_ntt_single_limb_single_poly():
     p = make_params(12, 1, 0, 0)
     orc, ctx = both(p)
