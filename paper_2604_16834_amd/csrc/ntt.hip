@@ -1099,7 +1099,7 @@ static void launch_hi_any(u32 log_hi, bool inverse, dim3 grid, hipStream_t st, c
 
 template <class A, int IT>
 static void launch_inv_lo_it(dim3 grid, hipStream_t st, const NttArgs& args, const PolyList& pl, bool mul = false) {
-    if constexpr (std::is_same<A, ArithF64>::value) {
+    if constexpr (std::is_same<A, ArithF64>::value && IT == 1) {  // the product-forming variant takes one item
         if (mul) {
             hipLaunchKernelGGL((ntt_inv_lo_kernel<A, IT, true>), grid, dim3(NTT_THREADS), 0, st, args, pl);
             return;
@@ -1144,7 +1144,7 @@ static void launch_lo_div(u32 items, dim3 grid, hipStream_t st, const NttArgs& a
 }
 template <class A>
 static void launch_inv_lo(u32 items, dim3 grid, hipStream_t st, const NttArgs& args, const PolyList& pl, bool mul = false) {
-    if (items == 2) launch_inv_lo_it<A, 2>(grid, st, args, pl, mul);
+    if (items == 2 && !mul) launch_inv_lo_it<A, 2>(grid, st, args, pl, false);
     else launch_inv_lo_it<A, 1>(grid, st, args, pl, mul);
 }
 
@@ -1229,7 +1229,8 @@ static hipError_t launch_ntt_any(const ckks_ctx* c, bool inverse, const u64* src
     const u32 slices = pl.n << c->log_hi;
     // batch items per lo-pass workgroup: in the inverse pass two share one fetch of the twiddles (an unrolled four cost too many
     // registers, and a loop over the items as in the plain forward pass spills in the variant that forms a product as it
-    // loads, 4.7 -> 6.3 ms per step of the block slice); the pass that ends a division takes one (with its epilogue's operands
+    // loads, 4.7 -> 6.3 ms per step of the block slice; that variant takes one item: with two it holds two operands' points a
+    // tile ahead and spills at three waves per SIMD, 4.7 against 4.2 ms per step for the class); the pass that ends a division takes one (with its epilogue's operands
     // two items leave only two waves per SIMD, which costs more than the second fetch of the twiddles); the plain forward
     // pass sets its own extent (launch_fwd_lo_loop)
     const u32 lo_items = (batch >= 2 && !epilogue) ? 2 : 1;
@@ -1281,7 +1282,12 @@ static hipError_t launch_ntt_any(const ckks_ctx* c, bool inverse, const u64* src
         args.last = c->log_hi == 0;
         {
             ProfScope ps__(c, K_NTT_INV_LO, st, mul_ptrs ? 1.5 * pass_bytes : pass_bytes, lo_ops);
-            if (mul_ptrs) launch_inv_lo<ArithF64>(lo_items, grid_lo, st, args, pl, true);
+            if (mul_ptrs) {  // one item per workgroup (see lo_items)
+                dim3 g1 = grid_lo;
+                if (args.lo_group) g1.y = batch;
+                else g1.x = batch;
+                launch_inv_lo<ArithF64>(1, g1, st, args, pl, true);
+            }
             else lo(args, pl);
         }
         if (c->log_hi > 0) { ProfScope ps__(c, K_NTT_INV_HI, st, pass_bytes, hi_ops); hi(second, pd); }
