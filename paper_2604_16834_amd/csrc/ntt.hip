@@ -1120,7 +1120,7 @@ static void launch_fwd_lo_loop(u32 batch, dim3 grid, hipStream_t st, const NttAr
     hipLaunchKernelGGL((ntt_fwd_lo_loop_kernel<A>), grid, dim3(NTT_THREADS), 0, st, args, pl);
 }
 template <class A>
-static void launch_lo_div(u32 items, dim3 grid, hipStream_t st, const NttArgs& args, const PolyList& pl, const FwdEpilogue& ep) {
+static void launch_lo_div(dim3 grid, hipStream_t st, const NttArgs& args, const PolyList& pl, const FwdEpilogue& ep) {
     // which optional operands the division's last step has is the same for the whole launch: one instantiation per case
     u32 n_add = 0, n_other = 0;
     const u32 n_ct = (args.batch + 1) / 2;
@@ -1130,16 +1130,11 @@ static void launch_lo_div(u32 items, dim3 grid, hipStream_t st, const NttArgs& a
         n_other += (fi.mask ? 1 : 0) + (fi.acc ? 1 : 0);
     }
     const int em = n_other ? 0 : (n_add == 2 * n_ct ? 1 : (n_add == 0 ? 2 : 0));
-#define LO_DIV_LAUNCH(IT, EM) hipLaunchKernelGGL((ntt_fwd_lo_div_kernel<A, IT, EM>), grid, dim3(NTT_THREADS), 0, st, args, pl, ep)
-    if (items == 2) {
-        if (em == 1) LO_DIV_LAUNCH(2, 1);
-        else if (em == 2) LO_DIV_LAUNCH(2, 2);
-        else LO_DIV_LAUNCH(2, 0);
-    } else {
-        if (em == 1) LO_DIV_LAUNCH(1, 1);
-        else if (em == 2) LO_DIV_LAUNCH(1, 2);
-        else LO_DIV_LAUNCH(1, 0);
-    }
+    // one batch item per workgroup (see lo_items in launch_ntt_any)
+#define LO_DIV_LAUNCH(EM) hipLaunchKernelGGL((ntt_fwd_lo_div_kernel<A, 1, EM>), grid, dim3(NTT_THREADS), 0, st, args, pl, ep)
+    if (em == 1) LO_DIV_LAUNCH(1);
+    else if (em == 2) LO_DIV_LAUNCH(2);
+    else LO_DIV_LAUNCH(0);
 #undef LO_DIV_LAUNCH
 }
 template <class A>
@@ -1268,8 +1263,8 @@ static hipError_t launch_ntt_any(const ckks_ctx* c, bool inverse, const u64* src
             if (hi_only) return hipGetLastError();  // the caller's own lo pass follows (launch_ntt_lo_mac)
             if (epilogue) {  // reads w and v, writes the quotients (plus the addends it reads)
                 ProfScope ps__(c, K_NTT_FWD_LO, st, (epilogue->use_vl == 2 ? 2.0 : 1.5) * pass_bytes, lo_ops);
-                if (f64) launch_lo_div<ArithF64>(lo_items, grid_lo, st, second, pd, *epilogue);
-                else launch_lo_div<ArithU64>(lo_items, grid_lo, st, second, pd, *epilogue);
+                if (f64) launch_lo_div<ArithF64>(grid_lo, st, second, pd, *epilogue);
+                else launch_lo_div<ArithU64>(grid_lo, st, second, pd, *epilogue);
             } else {
                 ProfScope ps__(c, K_NTT_FWD_LO, st, pass_bytes, lo_ops);
                 lo(second, pd);
