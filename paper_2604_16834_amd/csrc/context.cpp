@@ -285,7 +285,12 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
             }
         }
     }
-    // the conversion constants as doubles (value, value / target modulus) for the double-precision conversions
+    // the conversion constants as doubles for the double-precision conversions: the centred representative (f64m_dot takes
+    // centred operands) and its quotient by the target modulus
+    auto centred = [](u64 w, u64 q) {
+        const double v = w > (q >> 1) ? -(double)(q - w) : (double)w;
+        return TwF{v, v / (double)q};
+    };
     std::vector<TwF> modup_f, modup_prep_f, moddown_f, moddown_rs_f, moddown_prep_f, moddown_rs_prep_f, rescale_prep_f, rescale_conv_f;
     if (c->dnum && c->ntt_f64) {
         const u32 nq = c->num_q;
@@ -295,11 +300,9 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
                 const u64* tab = modup.data() + level * c->modup_level_stride() + j * c->modup_digit_stride();
                 TwF* tf = modup_f.data() + ((size_t)level * c->dnum + j) * M * c->alpha_pad;
                 for (u32 e = 0; e < c->ext_limbs(level); e++) {
-                    const double qt = (double)c->mod[c->ext_modulus(level, e)];
-                    for (u32 a = 0; a < c->alpha_pad; a++) {
-                        const double w = (double)tab[2 * c->alpha_pad + (size_t)e * c->alpha_pad + a];
-                        tf[(size_t)e * c->alpha_pad + a] = TwF{w, w / qt};
-                    }
+                    const u64 qt = c->mod[c->ext_modulus(level, e)];
+                    for (u32 a = 0; a < c->alpha_pad; a++)
+                        tf[(size_t)e * c->alpha_pad + a] = centred(tab[2 * c->alpha_pad + (size_t)e * c->alpha_pad + a], qt);
                 }
             }
         modup_prep_f.assign((size_t)nq * nq, TwF{0.0, 0.0});
@@ -314,10 +317,7 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
             }
         moddown_f.assign((size_t)nq * c->k_pad, TwF{0.0, 0.0});
         for (u32 i = 0; i < nq; i++)
-            for (u32 a = 0; a < c->k_pad; a++) {
-                const double w = (double)moddown[2 * c->k_pad + (size_t)i * c->k_pad + a];
-                moddown_f[(size_t)i * c->k_pad + a] = TwF{w, w / (double)c->mod[i]};
-            }
+            for (u32 a = 0; a < c->k_pad; a++) moddown_f[(size_t)i * c->k_pad + a] = centred(moddown[2 * c->k_pad + (size_t)i * c->k_pad + a], c->mod[i]);
         // what the inverse transform in front of ModDown scales a dropped limb by: 1/N times the limb's conversion constant
         auto prep = [&](u64 inv, u32 m) {
             const u64 q = c->mod[m];
@@ -341,10 +341,8 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
         for (u32 l = 1; l < nq; l++) {
             const u64* tab = moddown_rs.data() + l * c->moddown_rs_stride();
             for (u32 i = 0; i < l; i++)
-                for (u32 a = 0; a < c->k2_pad; a++) {
-                    const double w = (double)tab[2 * c->k2_pad + (size_t)i * c->k2_pad + a];
-                    moddown_rs_f[((size_t)l * nq + i) * c->k2_pad + a] = TwF{w, w / (double)c->mod[i]};
-                }
+                for (u32 a = 0; a < c->k2_pad; a++)
+                    moddown_rs_f[((size_t)l * nq + i) * c->k2_pad + a] = centred(tab[2 * c->k2_pad + (size_t)i * c->k2_pad + a], c->mod[i]);
         }
     }
     // rescale table [l][i] = (q_l^-1 mod q_i, Shoup companion, q_l mod q_i)

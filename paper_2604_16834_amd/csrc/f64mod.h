@@ -83,17 +83,35 @@ F64M_FN double f64m_centre(double t, double q) {
     return t > half ? t - q : (t < -half ? t + q : t);
 }
 
-// sum_{a < ND} y[a] * cw[a].w  mod q  (|y[a]| < 2^51) as a reduced double: the basis-conversion sum.  Partial sums of at
-// most eight products stay below 2^53; longer rows are reduced once on the way.
+// sum_{a < ND} y[a] * cw[a].w  mod q  as a reduced double, for centred operands: |y[a]| < 2^49 (centred residues of a
+// modulus below 2^50) and |cw[a].w| < 2^49 (the constant's centred representative; cw[a].wq is not read): the basis-conversion
+// sum.  Terms are taken in chains of up to eight.  A chain's running sum T starts at 1.5 * 2^102 and takes each product
+// with one fused multiply-add: the chain's sum stays below 2^101 in magnitude, so T stays in its binade and every step rounds
+// the exact sum to a multiple of 2^50.  D = T_new - T_old is exact; the step's remainder y w - D is an integer of magnitude at
+// most 2^49, which a second fused multiply-add gives exactly, and eight of them add up exactly (at most 2^52).  The chain's
+// high part T - 1.5 * 2^102, an exact multiple of 2^50, has a quotient by q below 2^51 in magnitude (2 max|y|), which
+// rint(high * (1/q)) misses by at most one; high - quotient * q, below 2q, is exact, the low part is added (below 2^53:
+// exact) and the sum reduced.  Four instructions per term, where a product reduced on its own takes seven.
+#define F64M_DOT_BASE 0x1.8p+102  /* 1.5 * 2^102 */
 template <int ND>
 F64M_FN double f64m_dot(const double* y, const TwF* cw, double q, double qinv) {
-    double s = 0.0;
+    double r = 0.0;
 #pragma unroll
-    for (int a = 0; a < ND; a++) {
-        s += f64m_mulmod(y[a], cw[a].w, cw[a].wq, q);
-        if (a == 7 && ND > 8) s = f64m_reduce(s, q, qinv);
+    for (int a0 = 0; a0 < ND; a0 += 8) {
+        double t = F64M_DOT_BASE, lo = 0.0;
+#pragma unroll
+        for (int a = a0; a < a0 + 8 && a < ND; a++) {
+            const double tn = __builtin_fma(y[a], cw[a].w, t);
+            const double d = tn - t;
+            lo += __builtin_fma(y[a], cw[a].w, -d);
+            t = tn;
+        }
+        const double hi = t - F64M_DOT_BASE;
+        const double c = __builtin_rint(hi * qinv);
+        const double v = f64m_reduce(__builtin_fma(-c, q, hi) + lo, q, qinv);
+        r = a0 == 0 ? v : f64m_reduce(r + v, q, qinv);
     }
-    return f64m_reduce(s, q, qinv);
+    return r;
 }
 
 // sum_s D[s] * c[s]  mod q  as a reduced double, for 32-bit signed D[s] and ND <= 13 constants c[s] < q given in three

@@ -46,7 +46,10 @@ int run_dot(const int64_t* y, const uint64_t* cw, uint32_t nd, uint64_t q, doubl
     TwF c[16];
     double yv[16];
     if (nd > 16) return -1;
-    for (uint32_t a = 0; a < nd; a++) c[a] = TwF{(double)cw[a], (double)cw[a] / qd};
+    for (uint32_t a = 0; a < nd; a++) {  // the constant's centred representative, as the library's tables hold it
+        const double w = cw[a] > (q >> 1) ? -(double)(q - cw[a]) : (double)cw[a];
+        c[a] = TwF{w, w / qd};
+    }
     for (size_t i = 0; i < n; i++) {
         for (uint32_t a = 0; a < nd; a++) yv[a] = (double)y[i * nd + a];
         switch (nd) {

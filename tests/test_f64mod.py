@@ -188,11 +188,13 @@ def test_centred_scaled_store(lib, q):
 
 
 @pytest.mark.parametrize("nd", [1, 4, 8, 9, 12, 16])
-@pytest.mark.parametrize("q", PRIMES[:5])
+@pytest.mark.parametrize("q", PRIMES)
 def test_conversion_sums(lib, q, nd):
-    """The basis-conversion sum of nd centred source residues times constants below q: exact although the partial sums of
-    eight products reach 8 * 0.63 q; inputs at their largest (|y| = 2^49 source residues of a 50-bit modulus, constants
-    q - 1 and the ones that put every product next to +-q/2) and random."""
+    """The basis-conversion sum of nd centred source residues times constants below q (their centred representatives): exact
+    although a chain of eight products reaches 2^101; inputs at their largest (|y| = 2^49 source residues of a 50-bit modulus
+    against the constants of largest magnitude, all of one sign and alternating), constants q - 1, powers of two that put
+    every product half way between two multiples of 2^50 (the chain's rounding ties), rows whose every product is congruent
+    to about +-q/2, and random."""
     rng = np.random.default_rng(q % 1000003 + nd)
     half_src = (1 << 49) - 1                                  # centred residues of a source modulus below 2^50
     n = 100_000
@@ -200,7 +202,12 @@ def test_conversion_sums(lib, q, nd):
     y[0] = half_src
     y[1] = -half_src
     y[2, ::2], y[2, 1::2] = half_src, -half_src
-    for cw in (rng.integers(0, q, size=nd, dtype=np.uint64), np.full(nd, q - 1, dtype=np.uint64), np.full(nd, (q + 1) // 2, dtype=np.uint64)):
+    y[40:2000] = 4 * rng.integers(-(half_src // 4), half_src // 4, size=(1960, nd), dtype=np.int64) + 2    # y = 2 mod 4
+    mixed = rng.integers(0, q, size=nd, dtype=np.uint64)
+    mixed[::2] = (q + 1) // 2                                  # centred -(q - 1) / 2 next to random constants
+    tie = min(1 << 48, 1 << (q.bit_length() - 2))              # y * 2^48 = 2^49 mod 2^50 for y = 2 mod 4
+    for cw in (rng.integers(0, q, size=nd, dtype=np.uint64), np.full(nd, q - 1, dtype=np.uint64), np.full(nd, (q + 1) // 2, dtype=np.uint64),
+               np.full(nd, (q - 1) // 2, dtype=np.uint64), np.full(nd, tie, dtype=np.uint64), mixed):
         cw = np.ascontiguousarray(cw)
         yy = y.copy()
         # rows whose every product is congruent to about +q/2: the sum of the per-term results is as large as it gets
