@@ -92,15 +92,19 @@ F64M_FN double f64m_centre(double t, double q) {
 // high part T - 1.5 * 2^102, an exact multiple of 2^50, has a quotient by q below 2^51 in magnitude (2 max|y|), which
 // rint(high * (1/q)) misses by at most one; high - quotient * q, below 2q, is exact, the low part is added (below 2^53:
 // exact) and the sum reduced.  Four instructions per term, where a product reduced on its own takes seven.
+// A row of nine terms (the division by P q_l: eight special primes and the dropped limb) is one chain too: only the ninth
+// step can take T past 2^103, where it rounds to a multiple of 2^51 and leaves a remainder of at most 2^50; D, the high
+// part and the sum of the remainders (at most 8 * 2^49 + 2^50) are still exact, the quotient stays below 2^52.
 #define F64M_DOT_BASE 0x1.8p+102  /* 1.5 * 2^102 */
 template <int ND>
 F64M_FN double f64m_dot(const double* y, const TwF* cw, double q, double qinv) {
+    constexpr int CHAIN = ND == 9 ? 9 : 8;
     double r = 0.0;
 #pragma unroll
-    for (int a0 = 0; a0 < ND; a0 += 8) {
+    for (int a0 = 0; a0 < ND; a0 += CHAIN) {
         double t = F64M_DOT_BASE, lo = 0.0;
 #pragma unroll
-        for (int a = a0; a < a0 + 8 && a < ND; a++) {
+        for (int a = a0; a < a0 + CHAIN && a < ND; a++) {
             const double tn = __builtin_fma(y[a], cw[a].w, t);
             const double d = tn - t;
             lo += __builtin_fma(y[a], cw[a].w, -d);
