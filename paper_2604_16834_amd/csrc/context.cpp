@@ -63,6 +63,7 @@ extern "C" void ckks_ctx_destroy(ckks_ctx* c) {
     (void)hipFree(c->d_tw);
     (void)hipFree(c->d_itw);
     (void)hipFree(c->d_twf);
+    (void)hipFree(c->d_twf_val);
     (void)hipFree(c->d_itwf);
     (void)hipFree(c->d_mcf);
     (void)hipFree(c->d_pow256);
@@ -371,6 +372,11 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
     if (e == hipSuccess) e = upload(tw, &c->d_tw);
     if (e == hipSuccess) e = upload(itw, &c->d_itw);
     if (e == hipSuccess) e = upload(twf, &c->d_twf);
+    {
+        std::vector<double> twf_val(twf.size());
+        for (size_t i = 0; i < twf.size(); i++) twf_val[i] = twf[i].w;
+        if (e == hipSuccess) e = upload(twf_val, &c->d_twf_val);
+    }
     if (e == hipSuccess) e = upload(itwf, &c->d_itwf);
     if (e == hipSuccess) e = upload(mcf, &c->d_mcf);
     if (e == hipSuccess) e = upload(pow256, &c->d_pow256);

@@ -62,7 +62,8 @@ F64M_FN double f64m_mulmod(double y, double w, double wq, double q) {
     return __builtin_fma(-c, q, h) + l;
 }
 
-// the same for a multiplier without a precomputed w / q: the quotient comes from the rounded product
+// the same for a multiplier without a precomputed w / q: the quotient comes from the rounded product (|y| < 2q: the quotient
+// is at most 1/2 + |y| / 2^52 off, the result at most q in magnitude)
 F64M_FN double f64m_mulmod_any(double y, double w, double q, double qinv) {
     const double h = y * w;
     const double l = __builtin_fma(y, w, -h);
@@ -97,7 +98,7 @@ F64M_FN double f64m_centre(double t, double q) {
 // part and the sum of the remainders (at most 8 * 2^49 + 2^50) are still exact, the quotient stays below 2^52.
 #define F64M_DOT_BASE 0x1.8p+102  /* 1.5 * 2^102 */
 template <int ND>
-F64M_FN double f64m_dot(const double* y, const TwF* cw, double q, double qinv) {
+F64M_FN double f64m_dot_w(const double* y, const double* w, double q, double qinv) {  // w[a]: the centred constants
     constexpr int CHAIN = ND == 9 ? 9 : 8;
     double r = 0.0;
 #pragma unroll
@@ -105,9 +106,9 @@ F64M_FN double f64m_dot(const double* y, const TwF* cw, double q, double qinv) {
         double t = F64M_DOT_BASE, lo = 0.0;
 #pragma unroll
         for (int a = a0; a < a0 + CHAIN && a < ND; a++) {
-            const double tn = __builtin_fma(y[a], cw[a].w, t);
+            const double tn = __builtin_fma(y[a], w[a], t);
             const double d = tn - t;
-            lo += __builtin_fma(y[a], cw[a].w, -d);
+            lo += __builtin_fma(y[a], w[a], -d);
             t = tn;
         }
         const double hi = t - F64M_DOT_BASE;
@@ -116,6 +117,13 @@ F64M_FN double f64m_dot(const double* y, const TwF* cw, double q, double qinv) {
         r = a0 == 0 ? v : f64m_reduce(r + v, q, qinv);
     }
     return r;
+}
+template <int ND>
+F64M_FN double f64m_dot(const double* y, const TwF* cw, double q, double qinv) {
+    double w[ND];
+#pragma unroll
+    for (int a = 0; a < ND; a++) w[a] = cw[a].w;
+    return f64m_dot_w<ND>(y, w, q, qinv);
 }
 
 // sum_s D[s] * c[s]  mod q  as a reduced double, for 32-bit signed D[s] and ND <= 13 constants c[s] < q given in three

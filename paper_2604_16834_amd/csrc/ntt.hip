@@ -144,6 +144,37 @@ __device__ __forceinline__ void inv_rows(typename A::E* v, const typename A::TW*
     }
 }
 
+// Butterflies whose twiddle is the value alone (no twiddle / q): the quotient comes from the rounded product.  Half the
+// registers and half the bytes per twiddle; from inputs reduced to q/2 + 1 the three stages of a round add at most 0.63 q,
+// 0.79 q and 0.98 q, so multiplicands stay below 2q and sums below 2^53 as with the precomputed quotient.
+struct ArithF64W : ArithF64 {
+    typedef double TW;
+    static __device__ __forceinline__ void fwd_bf(E& x, E& y, const double w, const MC& m) {
+        const double t = mulmod_any(y, w, m.q, m.qinv);
+        y = x - t;
+        x = x + t;
+    }
+};
+template <int S>
+__device__ __forceinline__ void load_tw_w(const double* __restrict__ tw, u32 T, double* tv) {
+#pragma unroll
+    for (int a = 0; a < S; a++)
+#pragma unroll
+        for (int j = 0; j < (1 << a); j++) tv[(1 << a) - 1 + j] = tw[(T << a) + j];
+}
+
+// what the forward lo passes hold of a twiddle and how they multiply by it: the value alone in double precision
+template <class A>
+struct LoFwd {
+    typedef A AR;
+    typedef typename A::TW TW;
+};
+template <>
+struct LoFwd<ArithF64> {
+    typedef ArithF64W AR;
+    typedef double TW;
+};
+
 // The same with the round's 2^S - 1 twiddles already in registers (tv[(1 << a) - 1 + j] = tw[(T << a) + j]):
 // the lo pass requests the twiddles of the next round before it starts the current one, so their
 // latency (they come from L2) hides behind a round of butterflies and an LDS exchange.
@@ -188,6 +219,7 @@ struct NttArgs {
     size_t dst_bstride;
     const void* mc;      // [M] ModConst or ModConstF
     const void* tw;      // [M][N] TwPair or TwF
+    const double* tw_val;  // [M][N] the twiddles' values alone (forward lo passes in double precision), or null
     u32 log_n, log_lo, log_hi;
     u32 first;           // this pass reads the caller's canonical residues (else the other pass's intermediate form)
     u32 last;            // this pass writes the final result (canonical; inverse: times 1/N)
@@ -233,6 +265,7 @@ struct PolyRef {
     const u64* src;
     u64* dst;
     const typename A::TW* tw;
+    const double* tw_val;  // this modulus' row of NttArgs::tw_val
     typename A::MC mc;
 };
 
@@ -246,8 +279,15 @@ __device__ __forceinline__ PolyRef<A> poly_ref(const NttArgs& args, const PolyLi
     r.src = (args.use_src_list ? args.src_list.p[b] : args.src + (((size_t)b * args.src_bstride) << args.log_n)) + ((size_t)sp << args.log_n);
     r.dst = args.dst + (((size_t)b * args.dst_bstride + dp) << args.log_n);
     r.tw = (const typename A::TW*)args.tw + ((size_t)m_idx << args.log_n);
+    r.tw_val = args.tw_val ? args.tw_val + ((size_t)m_idx << args.log_n) : nullptr;
     r.mc = ((const typename A::MC*)args.mc)[m_idx];
     return r;
+}
+
+template <class A, int S>
+__device__ __forceinline__ void load_fwd_tw(const PolyRef<A>& P, u32 T, typename LoFwd<A>::TW* tv) {
+    if constexpr (std::is_same<A, ArithF64>::value) load_tw_w<S>(P.tw_val, T, tv);
+    else load_tw<A, S>(P.tw, T, tv);
 }
 
 // ================================ lo pass (contiguous 2^11 blocks) ================================
@@ -288,12 +328,13 @@ __device__ __forceinline__ void fwd_lo_body(const NttArgs& args, const PolyList&
     const size_t off = (size_t)blk << 11;
     const u32 TA = (1u << args.log_hi) + blk;
     const u32 d3 = tid >> 5, x5 = tid & 31, d2 = (tid >> 2) & 7, d0 = tid & 3;
-    typedef typename A::TW TW;
+    typedef typename LoFwd<A>::TW TW;
+    typedef typename LoFwd<A>::AR AR;
     E v[8];
     u64 raw[8];
     TW wa[7], wb[7], wc[7], wd[6];
-    load_tw<A, 3>(P.tw, TA, wa);
-    load_tw<A, 3>(P.tw, 8 * TA + d3, wb);
+    load_fwd_tw<A, 3>(P, TA, wa);
+    load_fwd_tw<A, 3>(P, 8 * TA + d3, wb);
     {
         const u64* src = P.src + off;
 #pragma unroll
@@ -316,26 +357,26 @@ __device__ __forceinline__ void fwd_lo_body(const NttArgs& args, const PolyList&
 #pragma unroll
             for (int j = 0; j < 8; j++) raw[j] = src[tid + 256 * j];
         }
-        fwd_rows_pre<A, 3>(v, wa, P.mc);
+        fwd_rows_pre<AR, 3>(v, wa, P.mc);
         A::fwd_round_end(v, P.mc);
-        if (it == 0) load_tw<A, 3>(P.tw, 64 * TA + 8 * d3 + d2, wc);
+        if (it == 0) load_fwd_tw<A, 3>(P, 64 * TA + 8 * d3 + d2, wc);
 #pragma unroll
         for (int j = 0; j < 8; j++) buf0[LDS_PAD(tid + 256 * j)] = v[j];
         __syncthreads();
 #pragma unroll
         for (int j = 0; j < 8; j++) v[j] = buf0[LDS_PAD(d3 * 256 + 32 * j + x5)];
-        fwd_rows_pre<A, 3>(v, wb, P.mc);
+        fwd_rows_pre<AR, 3>(v, wb, P.mc);
         A::fwd_round_end(v, P.mc);
         if (it == 0) {
-            load_tw<A, 2>(P.tw, 512 * TA + 2 * tid, wd);
-            load_tw<A, 2>(P.tw, 512 * TA + 2 * tid + 1, wd + 3);
+            load_fwd_tw<A, 2>(P, 512 * TA + 2 * tid, wd);
+            load_fwd_tw<A, 2>(P, 512 * TA + 2 * tid + 1, wd + 3);
         }
 #pragma unroll
         for (int j = 0; j < 8; j++) buf1[LDS_PAD(d3 * 256 + 32 * j + x5)] = v[j];
         __syncthreads();
 #pragma unroll
         for (int j = 0; j < 8; j++) v[j] = buf1[LDS_PAD(d3 * 256 + d2 * 32 + 4 * j + d0)];
-        fwd_rows_pre<A, 3>(v, wc, P.mc);
+        fwd_rows_pre<AR, 3>(v, wc, P.mc);
         A::fwd_round_end(v, P.mc);
 #pragma unroll
         for (int j = 0; j < 8; j++) buf0[LDS_PAD(d3 * 256 + d2 * 32 + 4 * j + d0)] = v[j];
@@ -366,8 +407,8 @@ __device__ __forceinline__ void fwd_lo_body(const NttArgs& args, const PolyList&
                 }
             }
         }
-        fwd_rows_pre<A, 2>(v, wd, P.mc);
-        fwd_rows_pre<A, 2>(v + 4, wd + 3, P.mc);
+        fwd_rows_pre<AR, 2>(v, wd, P.mc);
+        fwd_rows_pre<AR, 2>(v + 4, wd + 3, P.mc);
         A::fwd_round_end(v, P.mc);
         // back through LDS so that a wave stores 512 contiguous bytes per instruction
 #pragma unroll
@@ -449,7 +490,8 @@ __device__ __forceinline__ void fwd_lo_body(const NttArgs& args, const PolyList&
 template <class A>
 __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_loop_kernel(NttArgs args, PolyList pl) {
     typedef typename A::E E;
-    typedef typename A::TW TW;
+    typedef typename LoFwd<A>::TW TW;
+    typedef typename LoFwd<A>::AR AR;
     __shared__ E lds0[LDS_PADDED_WORDS];
     __shared__ E lds1[LDS_PADDED_WORDS];
     const u32 tid = threadIdx.x;
@@ -463,16 +505,16 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_loop_kernel(NttArgs ar
     E v[8];
     u64 raw[8];
     TW wa[7], wb[7], wc[7], wd[6];
-    load_tw<A, 3>(P.tw, TA, wa);
+    load_fwd_tw<A, 3>(P, TA, wa);
     {
         const u64* src = P.src + off;
 #pragma unroll
         for (int j = 0; j < 8; j++) raw[j] = src[tid + 256 * j];
     }
-    load_tw<A, 3>(P.tw, 8 * TA + d3, wb);
-    load_tw<A, 3>(P.tw, 64 * TA + 8 * d3 + d2, wc);
-    load_tw<A, 2>(P.tw, 512 * TA + 2 * tid, wd);
-    load_tw<A, 2>(P.tw, 512 * TA + 2 * tid + 1, wd + 3);
+    load_fwd_tw<A, 3>(P, 8 * TA + d3, wb);
+    load_fwd_tw<A, 3>(P, 64 * TA + 8 * d3 + d2, wc);
+    load_fwd_tw<A, 2>(P, 512 * TA + 2 * tid, wd);
+    load_fwd_tw<A, 2>(P, 512 * TA + 2 * tid + 1, wd + 3);
     for (u32 b = tile.b; b < args.batch; b += b_step) {
         if (args.first) {
 #pragma unroll
@@ -486,29 +528,29 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_loop_kernel(NttArgs ar
 #pragma unroll
             for (int j = 0; j < 8; j++) raw[j] = src[tid + 256 * j];
         }
-        fwd_rows_pre<A, 3>(v, wa, P.mc);
+        fwd_rows_pre<AR, 3>(v, wa, P.mc);
         A::fwd_round_end(v, P.mc);
 #pragma unroll
         for (int j = 0; j < 8; j++) lds0[LDS_PAD(tid + 256 * j)] = v[j];
         __syncthreads();
 #pragma unroll
         for (int j = 0; j < 8; j++) v[j] = lds0[LDS_PAD(d3 * 256 + 32 * j + x5)];
-        fwd_rows_pre<A, 3>(v, wb, P.mc);
+        fwd_rows_pre<AR, 3>(v, wb, P.mc);
         A::fwd_round_end(v, P.mc);
 #pragma unroll
         for (int j = 0; j < 8; j++) lds1[LDS_PAD(d3 * 256 + 32 * j + x5)] = v[j];
         __syncthreads();
 #pragma unroll
         for (int j = 0; j < 8; j++) v[j] = lds1[LDS_PAD(d3 * 256 + d2 * 32 + 4 * j + d0)];
-        fwd_rows_pre<A, 3>(v, wc, P.mc);
+        fwd_rows_pre<AR, 3>(v, wc, P.mc);
         A::fwd_round_end(v, P.mc);
 #pragma unroll
         for (int j = 0; j < 8; j++) lds0[LDS_PAD(d3 * 256 + d2 * 32 + 4 * j + d0)] = v[j];
         __syncthreads();
 #pragma unroll
         for (int j = 0; j < 8; j++) v[j] = lds0[LDS_PAD(8 * tid + j)];
-        fwd_rows_pre<A, 2>(v, wd, P.mc);
-        fwd_rows_pre<A, 2>(v + 4, wd + 3, P.mc);
+        fwd_rows_pre<AR, 2>(v, wd, P.mc);
+        fwd_rows_pre<AR, 2>(v + 4, wd + 3, P.mc);
         A::fwd_round_end(v, P.mc);
         // back through LDS so that a wave stores 512 contiguous bytes per instruction
 #pragma unroll
@@ -570,19 +612,20 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_mac_kernel(NttArgs arg
     // points before it is done with the previous item
     const u32 b_step = args.lo_group ? gridDim.y : gridDim.x;
     const size_t N = (size_t)1 << args.log_n, off = (size_t)blk << 11;
-    const TwF* tw = (const TwF*)args.tw + ((size_t)m_idx << args.log_n);
+    const double* tw = args.tw_val + ((size_t)m_idx << args.log_n);
     const ModConstF mc = ((const ModConstF*)args.mc)[m_idx];
     const u32 own = e <= ep.level ? e / ep.D.alpha : 0xffffffffu;  // the digit that limb e belongs to
     const u32 TA = (1u << args.log_hi) + blk;
     const u32 d3 = tid >> 5, x5 = tid & 31, d2 = (tid >> 2) & 7, d0 = tid & 3;
     const size_t kstride = (size_t)ep.M * N;  // between the b and the a part of a digit's key; two of them per digit
     const size_t dstride = (size_t)ep.E * N;
-    TwF wa[7], wb[7], wc[7], wd[6];  // the slice's twiddles, fetched once for all digits of all items
-    load_tw<A, 3>(tw, TA, wa);
-    load_tw<A, 3>(tw, 8 * TA + d3, wb);
-    load_tw<A, 3>(tw, 64 * TA + 8 * d3 + d2, wc);
-    load_tw<A, 2>(tw, 512 * TA + 2 * tid, wd);
-    load_tw<A, 2>(tw, 512 * TA + 2 * tid + 1, wd + 3);
+    typedef ArithF64W AW;
+    double wa[7], wb[7], wc[7], wd[6];  // the slice's twiddles, fetched once for all digits of all items
+    load_tw_w<3>(tw, TA, wa);
+    load_tw_w<3>(tw, 8 * TA + d3, wb);
+    load_tw_w<3>(tw, 64 * TA + 8 * d3 + d2, wc);
+    load_tw_w<2>(tw, 512 * TA + 2 * tid, wd);
+    load_tw_w<2>(tw, 512 * TA + 2 * tid + 1, wd + 3);
     const u32 j0 = own == 0 ? 1 : 0;  // first digit to transform
     E v[8], raw[8];
     if (j0 < ep.beta) {
@@ -606,21 +649,21 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_mac_kernel(NttArgs arg
 #pragma unroll
             for (int i = 0; i < 8; i++) raw[i] = hi[(size_t)jn * dstride + tid + 256 * i];
         }
-        fwd_rows_pre<A, 3>(v, wa, mc);
+        fwd_rows_pre<AW, 3>(v, wa, mc);
         A::fwd_round_end(v, mc);
 #pragma unroll
         for (int i = 0; i < 8; i++) lds0[LDS_PAD(tid + 256 * i)] = v[i];
         __syncthreads();
 #pragma unroll
         for (int i = 0; i < 8; i++) v[i] = lds0[LDS_PAD(d3 * 256 + 32 * i + x5)];
-        fwd_rows_pre<A, 3>(v, wb, mc);
+        fwd_rows_pre<AW, 3>(v, wb, mc);
         A::fwd_round_end(v, mc);
 #pragma unroll
         for (int i = 0; i < 8; i++) lds1[LDS_PAD(d3 * 256 + 32 * i + x5)] = v[i];
         __syncthreads();
 #pragma unroll
         for (int i = 0; i < 8; i++) v[i] = lds1[LDS_PAD(d3 * 256 + d2 * 32 + 4 * i + d0)];
-        fwd_rows_pre<A, 3>(v, wc, mc);
+        fwd_rows_pre<AW, 3>(v, wc, mc);
         A::fwd_round_end(v, mc);
 #pragma unroll
         for (int i = 0; i < 8; i++) lds0[LDS_PAD(d3 * 256 + d2 * 32 + 4 * i + d0)] = v[i];
@@ -637,8 +680,8 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_mac_kernel(NttArgs arg
                 k1[i] = kj[kstride + tid + 256 * i];
             }
         }
-        fwd_rows_pre<A, 2>(v, wd, mc);
-        fwd_rows_pre<A, 2>(v + 4, wd + 3, mc);
+        fwd_rows_pre<AW, 2>(v, wd, mc);
+        fwd_rows_pre<AW, 2>(v + 4, wd + 3, mc);
         A::fwd_round_end(v, mc);
         // back through LDS: point tid + 256 i of the slice, where the key words were fetched
 #pragma unroll
@@ -911,9 +954,9 @@ __device__ __forceinline__ void conv_load(double (&yv)[AP], const double* __rest
     for (int a = 0; a < ND; a++) yv[a] = yp[(size_t)((u32)a < nd ? a : nd - 1) * N];
 }
 template <int AP, int ND>
-__device__ __forceinline__ double conv_sum(const double (&yv)[AP], const TwF* cw, double q, double qinv) {
+__device__ __forceinline__ double conv_sum(const double (&yv)[AP], const double* cw, double q, double qinv) {
     static_assert(ND <= 8 || AP > 8, "rows of more than eight entries are padded to twelve or sixteen");
-    return f64m_dot<ND>(yv, cw, q, qinv);
+    return f64m_dot_w<ND>(yv, cw, q, qinv);
 }
 
 // One workgroup converts and transforms the same tile of T target limbs: the source residues are fetched once for all T
@@ -928,14 +971,14 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_hi_conv_kernel(NttArgs ar
     const size_t N = (size_t)1 << args.log_n;
     const double* y = cp.y + b * cp.y_bstride + (size_t)cp.lo * N + (size_t)tile * CC;
     PolyRef<A> P[T];
-    TwF cw[T][AP];
+    double cw[T][ND];  // the centred constants (the tables' quotients by the modulus are not read)
 #pragma unroll
     for (int t = 0; t < T; t++) {
         const u32 a_idx = a0 + t < pl.n ? a0 + t : pl.n - 1;  // a ragged last group repeats its last limb and skips the store
         P[t] = poly_ref<A, true>(args, pl, b, a_idx);
         const TwF* ce = cp.convf + (size_t)pl.dpos[a_idx] * AP;
 #pragma unroll
-        for (int a = 0; a < AP; a++) cw[t][a] = ce[a];
+        for (int a = 0; a < ND; a++) cw[t][a] = ce[a].w;
     }
     E v[T][8];
     if constexpr (LOG_HI <= 3) {
@@ -1189,6 +1232,7 @@ static hipError_t launch_ntt_any(const ckks_ctx* c, bool inverse, const u64* src
     args.dst_bstride = dst_bstride;
     args.mc = f64 ? (const void*)c->d_mcf : (const void*)c->d_mc;
     args.tw = f64 ? (const void*)(inverse ? c->d_itwf : c->d_twf) : (const void*)(inverse ? c->d_itw : c->d_tw);
+    args.tw_val = (f64 && !inverse) ? c->d_twf_val : nullptr;
     args.log_n = c->log_n;
     args.log_lo = c->log_lo;
     args.log_hi = c->log_hi;
@@ -1334,6 +1378,7 @@ hipError_t launch_ntt_lo_mac(const ckks_ctx* c, u32 level, const DigitSrc& digit
     NttArgs args = {};
     args.mc = c->d_mcf;
     args.tw = c->d_twf;
+    args.tw_val = c->d_twf_val;
     args.log_n = c->log_n;
     args.log_lo = c->log_lo;
     args.log_hi = c->log_hi;

@@ -66,7 +66,11 @@ int run_dot(const int64_t* y, const uint64_t* cw, uint32_t nd, uint64_t q, doubl
 }
 // three forward butterfly stages on eight values (a round of the transforms), then the round's reduction; returns the
 // largest multiplicand magnitude seen, so that the caller can check the "below 2^51" precondition along the way
-double run_fwd_round(int64_t* v8, const uint64_t* tw7, uint64_t q) {
+static double fwd_round(int64_t* v8, const uint64_t* tw7, uint64_t q, bool value_only);
+double run_fwd_round(int64_t* v8, const uint64_t* tw7, uint64_t q) { return fwd_round(v8, tw7, q, false); }
+// the same with twiddles given as values alone (the quotient from the rounded product: f64m_mulmod_any)
+double run_fwd_round_any(int64_t* v8, const uint64_t* tw7, uint64_t q) { return fwd_round(v8, tw7, q, true); }
+static double fwd_round(int64_t* v8, const uint64_t* tw7, uint64_t q, bool value_only) {
     const double qd = (double)q, qinv = 1.0 / qd;
     double v[8], worst = 0.0;
     for (int j = 0; j < 8; j++) v[j] = (double)v8[j];
@@ -77,7 +81,7 @@ double run_fwd_round(int64_t* v8, const uint64_t* tw7, uint64_t q) {
             const double w = (double)tw7[(1 << a) - 1 + (rr >> (3 - a))];
             const double y = v[rr + half];
             if (__builtin_fabs(y) > worst) worst = __builtin_fabs(y);
-            const double t = f64m_mulmod(y, w, w / qd, qd);
+            const double t = value_only ? f64m_mulmod_any(y, w, qd, qinv) : f64m_mulmod(y, w, w / qd, qd);
             v[rr + half] = v[rr] - t;
             v[rr] = v[rr] + t;
         }

@@ -31,6 +31,7 @@ def build_checker(out_dir):
     lib.chk_dot.restype = ctypes.c_long
     lib.chk_fold.restype = ctypes.c_long
     lib.run_fwd_round.restype = ctypes.c_double
+    lib.run_fwd_round_any.restype = ctypes.c_double
     return lib
 
 
@@ -122,7 +123,7 @@ def test_mulmod_precomputed_quotient(lib, q):
 @pytest.mark.parametrize("q", PRIMES)
 def test_mulmod_data_multiplier(lib, q):
     """mulmod_any (quotient from the rounded product): |y| < q, 0 <= w < q: exact, at most (1/2 + |y| / 2^52) q < 3/4 q;
-    below 0.63 q for reduced multiplicands."""
+    below 0.63 q for reduced multiplicands; exact and at most q for |y| < 2q."""
     rng = np.random.default_rng(q % 1000003 + 1)
     edge_y = boundary_multiplicands(q, q)
     edge_w = np.array(sorted({0, 1, 2, q // 2, (q + 1) // 2, q - 2, q - 1}), dtype=np.uint64)
@@ -140,6 +141,14 @@ def test_mulmod_data_multiplier(lib, q):
     check_product(lib, lib.run_mulmod_any, y, w, q, 63, 100)
     y, w = near_tie_pairs(q, rng, 20000, half)
     check_product(lib, lib.run_mulmod_any, y, w, q, 63, 100)
+    # as a butterfly's twiddle product (the lo passes hold a twiddle's value alone): multiplicands up to 2q, at most q
+    wide = 2 * q
+    yy, ww = np.meshgrid(boundary_multiplicands(q, wide), edge_w)
+    check_product(lib, lib.run_mulmod_any, yy.ravel(), ww.ravel(), q, 1, 1)
+    y = rng.integers(-(wide - 1), wide, size=n, dtype=np.int64)
+    check_product(lib, lib.run_mulmod_any, y, rng.integers(0, q, size=n, dtype=np.uint64), q, 1, 1)
+    y, w = near_tie_pairs(q, rng, 20000, wide)
+    check_product(lib, lib.run_mulmod_any, y, w, q, 1, 1)
 
 
 @pytest.mark.parametrize("q", PRIMES)
@@ -223,10 +232,12 @@ def test_conversion_sums(lib, q, nd):
         assert bad < 0, f"q={q} nd={nd}: row {yy[bad].tolist()} gave {r[bad]!r}"
 
 
+@pytest.mark.parametrize("fn", ["run_fwd_round", "run_fwd_round_any"])
 @pytest.mark.parametrize("q", PRIMES[:5])
-def test_forward_round_of_three_stages(lib, q):
+def test_forward_round_of_three_stages(lib, q, fn):
     """Three butterfly stages on reduced inputs and the reduction that ends the round, as the transforms chain them:
-    every multiplicand stays below 2q (so below 2^51), the results match exact integer butterflies."""
+    every multiplicand stays below 2q (so below 2^51), the results match exact integer butterflies.  With the twiddle's
+    quotient precomputed, and with the twiddle's value alone (the fused inner-product pass)."""
     rng = np.random.default_rng(q % 1000003 + 5)
     half = q // 2 + 1
     worst = 0.0
@@ -240,7 +251,7 @@ def test_forward_round_of_three_stages(lib, q):
         want = np.empty(8, dtype=np.uint64)
         lib.ref_fwd_round(ptr(v), ptr(tw), ctypes.c_uint64(q), ptr(want))
         got = v.copy()
-        worst = max(worst, lib.run_fwd_round(ptr(got), ptr(tw), ctypes.c_uint64(q)))
+        worst = max(worst, getattr(lib, fn)(ptr(got), ptr(tw), ctypes.c_uint64(q)))
         assert np.all(np.abs(got) <= half), (q, trial)
         assert np.array_equal(np.mod(got, q).astype(np.uint64), want), (q, trial)
     assert worst < 2 * q
