@@ -64,6 +64,7 @@ extern "C" void ckks_ctx_destroy(ckks_ctx* c) {
     (void)hipFree(c->d_itw);
     (void)hipFree(c->d_twf);
     (void)hipFree(c->d_twf_val);
+    (void)hipFree(c->d_itwf_val);
     (void)hipFree(c->d_itwf);
     (void)hipFree(c->d_mcf);
     (void)hipFree(c->d_pow256);
@@ -376,6 +377,8 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
         std::vector<double> twf_val(twf.size());
         for (size_t i = 0; i < twf.size(); i++) twf_val[i] = twf[i].w;
         if (e == hipSuccess) e = upload(twf_val, &c->d_twf_val);
+        for (size_t i = 0; i < itwf.size(); i++) twf_val[i] = itwf[i].w;
+        if (e == hipSuccess) e = upload(twf_val, &c->d_itwf_val);
     }
     if (e == hipSuccess) e = upload(itwf, &c->d_itwf);
     if (e == hipSuccess) e = upload(mcf, &c->d_mcf);

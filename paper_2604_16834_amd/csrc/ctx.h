@@ -135,7 +135,8 @@ struct ckks_ctx {
     bool ntt_f64 = false;             // moduli below 2^50 and N >= 2^11: double-precision butterflies, tables below instead
     TwF* d_twf = nullptr;             // [M][N]  psi^bitrev(i) and psi^bitrev(i) / q as doubles
     TwF* d_itwf = nullptr;
-    double* d_twf_val = nullptr;      // [M][N]  psi^bitrev(i) alone: what the forward lo passes read (half the bytes of d_twf)
+    double* d_twf_val = nullptr;      // [M][N]  psi^bitrev(i) alone: what the lo passes read (half the bytes of d_twf)
+    double* d_itwf_val = nullptr;
     ModConstF* d_mcf = nullptr;       // [M]
     double* d_pow256 = nullptr;       // [M][POW256_ROW]: 2^(8s) mod q, s < 13, in parts of 17, 17 and 16 bits, then 2^17 mod q and its quotient by q (moduli below 2^50 only)
     u64* d_modup = nullptr;           // per level, per digit: see modup_digit_stride()

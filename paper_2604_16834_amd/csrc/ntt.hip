@@ -154,6 +154,12 @@ struct ArithF64W : ArithF64 {
         y = x - t;
         x = x + t;
     }
+    // the inverse butterfly: the sum is re-centred, the difference (below 2q) times the twiddle is at most q
+    static __device__ __forceinline__ void inv_bf(E& x, E& y, const double w, const MC& m) {
+        const double s = x + y, d = x - y;
+        x = reduce(s, m);
+        y = mulmod_any(d, w, m.q, m.qinv);
+    }
 };
 template <int S>
 __device__ __forceinline__ void load_tw_w(const double* __restrict__ tw, u32 T, double* tv) {
@@ -163,14 +169,14 @@ __device__ __forceinline__ void load_tw_w(const double* __restrict__ tw, u32 T, 
         for (int j = 0; j < (1 << a); j++) tv[(1 << a) - 1 + j] = tw[(T << a) + j];
 }
 
-// what the forward lo passes hold of a twiddle and how they multiply by it: the value alone in double precision
+// what the lo passes hold of a twiddle and how they multiply by it: the value alone in double precision
 template <class A>
-struct LoFwd {
+struct LoTw {
     typedef A AR;
     typedef typename A::TW TW;
 };
 template <>
-struct LoFwd<ArithF64> {
+struct LoTw<ArithF64> {
     typedef ArithF64W AR;
     typedef double TW;
 };
@@ -219,7 +225,7 @@ struct NttArgs {
     size_t dst_bstride;
     const void* mc;      // [M] ModConst or ModConstF
     const void* tw;      // [M][N] TwPair or TwF
-    const double* tw_val;  // [M][N] the twiddles' values alone (forward lo passes in double precision), or null
+    const double* tw_val;  // [M][N] the twiddles' values alone (lo passes in double precision), or null
     u32 log_n, log_lo, log_hi;
     u32 first;           // this pass reads the caller's canonical residues (else the other pass's intermediate form)
     u32 last;            // this pass writes the final result (canonical; inverse: times 1/N)
@@ -285,7 +291,7 @@ __device__ __forceinline__ PolyRef<A> poly_ref(const NttArgs& args, const PolyLi
 }
 
 template <class A, int S>
-__device__ __forceinline__ void load_fwd_tw(const PolyRef<A>& P, u32 T, typename LoFwd<A>::TW* tv) {
+__device__ __forceinline__ void load_lo_tw(const PolyRef<A>& P, u32 T, typename LoTw<A>::TW* tv) {
     if constexpr (std::is_same<A, ArithF64>::value) load_tw_w<S>(P.tw_val, T, tv);
     else load_tw<A, S>(P.tw, T, tv);
 }
@@ -328,13 +334,13 @@ __device__ __forceinline__ void fwd_lo_body(const NttArgs& args, const PolyList&
     const size_t off = (size_t)blk << 11;
     const u32 TA = (1u << args.log_hi) + blk;
     const u32 d3 = tid >> 5, x5 = tid & 31, d2 = (tid >> 2) & 7, d0 = tid & 3;
-    typedef typename LoFwd<A>::TW TW;
-    typedef typename LoFwd<A>::AR AR;
+    typedef typename LoTw<A>::TW TW;
+    typedef typename LoTw<A>::AR AR;
     E v[8];
     u64 raw[8];
     TW wa[7], wb[7], wc[7], wd[6];
-    load_fwd_tw<A, 3>(P, TA, wa);
-    load_fwd_tw<A, 3>(P, 8 * TA + d3, wb);
+    load_lo_tw<A, 3>(P, TA, wa);
+    load_lo_tw<A, 3>(P, 8 * TA + d3, wb);
     {
         const u64* src = P.src + off;
 #pragma unroll
@@ -359,7 +365,7 @@ __device__ __forceinline__ void fwd_lo_body(const NttArgs& args, const PolyList&
         }
         fwd_rows_pre<AR, 3>(v, wa, P.mc);
         A::fwd_round_end(v, P.mc);
-        if (it == 0) load_fwd_tw<A, 3>(P, 64 * TA + 8 * d3 + d2, wc);
+        if (it == 0) load_lo_tw<A, 3>(P, 64 * TA + 8 * d3 + d2, wc);
 #pragma unroll
         for (int j = 0; j < 8; j++) buf0[LDS_PAD(tid + 256 * j)] = v[j];
         __syncthreads();
@@ -368,8 +374,8 @@ __device__ __forceinline__ void fwd_lo_body(const NttArgs& args, const PolyList&
         fwd_rows_pre<AR, 3>(v, wb, P.mc);
         A::fwd_round_end(v, P.mc);
         if (it == 0) {
-            load_fwd_tw<A, 2>(P, 512 * TA + 2 * tid, wd);
-            load_fwd_tw<A, 2>(P, 512 * TA + 2 * tid + 1, wd + 3);
+            load_lo_tw<A, 2>(P, 512 * TA + 2 * tid, wd);
+            load_lo_tw<A, 2>(P, 512 * TA + 2 * tid + 1, wd + 3);
         }
 #pragma unroll
         for (int j = 0; j < 8; j++) buf1[LDS_PAD(d3 * 256 + 32 * j + x5)] = v[j];
@@ -490,8 +496,8 @@ __device__ __forceinline__ void fwd_lo_body(const NttArgs& args, const PolyList&
 template <class A>
 __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_loop_kernel(NttArgs args, PolyList pl) {
     typedef typename A::E E;
-    typedef typename LoFwd<A>::TW TW;
-    typedef typename LoFwd<A>::AR AR;
+    typedef typename LoTw<A>::TW TW;
+    typedef typename LoTw<A>::AR AR;
     __shared__ E lds0[LDS_PADDED_WORDS];
     __shared__ E lds1[LDS_PADDED_WORDS];
     const u32 tid = threadIdx.x;
@@ -505,16 +511,16 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_loop_kernel(NttArgs ar
     E v[8];
     u64 raw[8];
     TW wa[7], wb[7], wc[7], wd[6];
-    load_fwd_tw<A, 3>(P, TA, wa);
+    load_lo_tw<A, 3>(P, TA, wa);
     {
         const u64* src = P.src + off;
 #pragma unroll
         for (int j = 0; j < 8; j++) raw[j] = src[tid + 256 * j];
     }
-    load_fwd_tw<A, 3>(P, 8 * TA + d3, wb);
-    load_fwd_tw<A, 3>(P, 64 * TA + 8 * d3 + d2, wc);
-    load_fwd_tw<A, 2>(P, 512 * TA + 2 * tid, wd);
-    load_fwd_tw<A, 2>(P, 512 * TA + 2 * tid + 1, wd + 3);
+    load_lo_tw<A, 3>(P, 8 * TA + d3, wb);
+    load_lo_tw<A, 3>(P, 64 * TA + 8 * d3 + d2, wc);
+    load_lo_tw<A, 2>(P, 512 * TA + 2 * tid, wd);
+    load_lo_tw<A, 2>(P, 512 * TA + 2 * tid + 1, wd + 3);
     for (u32 b = tile.b; b < args.batch; b += b_step) {
         if (args.first) {
 #pragma unroll
@@ -788,13 +794,14 @@ __global__ __launch_bounds__(NTT_THREADS) __attribute__((amdgpu_waves_per_eu(3, 
     const size_t off = (size_t)blk << 11;
     const u32 TA = (1u << args.log_hi) + blk;
     const u32 d3 = tid >> 5, x5 = tid & 31, d2 = (tid >> 2) & 7, d0 = tid & 3;
-    typedef typename A::TW TW;
+    typedef typename LoTw<A>::TW TW;
+    typedef typename LoTw<A>::AR AR;
     E v[8];
     ulonglong2 raw[4], raw2[MUL ? 4 : 1];
     TW wa[7], wb[7], wc[7], wd[6];
-    load_tw<A, 2>(P.tw, 512 * TA + 2 * tid, wd);
-    load_tw<A, 2>(P.tw, 512 * TA + 2 * tid + 1, wd + 3);
-    load_tw<A, 3>(P.tw, 64 * TA + 8 * d3 + d2, wc);
+    load_lo_tw<A, 2>(P, 512 * TA + 2 * tid, wd);
+    load_lo_tw<A, 2>(P, 512 * TA + 2 * tid + 1, wd + 3);
+    load_lo_tw<A, 3>(P, 64 * TA + 8 * d3 + d2, wc);
     const size_t moff = ((size_t)pl_at(pl.spos, tile.a) << args.log_n) + off + 8 * tid;  // MUL: the multiplier's point
     {
         const ulonglong2* in = reinterpret_cast<const ulonglong2*>(P.src + off + 8 * tid);
@@ -845,28 +852,28 @@ __global__ __launch_bounds__(NTT_THREADS) __attribute__((amdgpu_waves_per_eu(3, 
                 for (int j = 0; j < 4; j++) raw2[j] = in2[j];
             }
         }
-        inv_rows_pre<A, 2>(v, wd, P.mc);
-        inv_rows_pre<A, 2>(v + 4, wd + 3, P.mc);
-        if (it == 0) load_tw<A, 3>(P.tw, 8 * TA + d3, wb);
+        inv_rows_pre<AR, 2>(v, wd, P.mc);
+        inv_rows_pre<AR, 2>(v + 4, wd + 3, P.mc);
+        if (it == 0) load_lo_tw<A, 3>(P, 8 * TA + d3, wb);
 #pragma unroll
         for (int j = 0; j < 8; j++) buf0[LDS_PAD(8 * tid + j)] = v[j];
         __syncthreads();
 #pragma unroll
         for (int j = 0; j < 8; j++) v[j] = buf0[LDS_PAD(d3 * 256 + d2 * 32 + 4 * j + d0)];
-        inv_rows_pre<A, 3>(v, wc, P.mc);
-        if (it == 0) load_tw<A, 3>(P.tw, TA, wa);
+        inv_rows_pre<AR, 3>(v, wc, P.mc);
+        if (it == 0) load_lo_tw<A, 3>(P, TA, wa);
 #pragma unroll
         for (int j = 0; j < 8; j++) buf1[LDS_PAD(d3 * 256 + d2 * 32 + 4 * j + d0)] = v[j];
         __syncthreads();
 #pragma unroll
         for (int j = 0; j < 8; j++) v[j] = buf1[LDS_PAD(d3 * 256 + 32 * j + x5)];
-        inv_rows_pre<A, 3>(v, wb, P.mc);
+        inv_rows_pre<AR, 3>(v, wb, P.mc);
 #pragma unroll
         for (int j = 0; j < 8; j++) buf0[LDS_PAD(d3 * 256 + 32 * j + x5)] = v[j];
         __syncthreads();
 #pragma unroll
         for (int j = 0; j < 8; j++) v[j] = buf0[LDS_PAD(tid + 256 * j)];
-        inv_rows_pre<A, 3>(v, wa, P.mc);
+        inv_rows_pre<AR, 3>(v, wa, P.mc);
         u64* dst = item_dst(args, pl, b0 + it, tile.a) + off;
         if (args.last) {
 #pragma unroll
@@ -1232,7 +1239,7 @@ static hipError_t launch_ntt_any(const ckks_ctx* c, bool inverse, const u64* src
     args.dst_bstride = dst_bstride;
     args.mc = f64 ? (const void*)c->d_mcf : (const void*)c->d_mc;
     args.tw = f64 ? (const void*)(inverse ? c->d_itwf : c->d_twf) : (const void*)(inverse ? c->d_itw : c->d_tw);
-    args.tw_val = (f64 && !inverse) ? c->d_twf_val : nullptr;
+    args.tw_val = f64 ? (inverse ? c->d_itwf_val : c->d_twf_val) : nullptr;
     args.log_n = c->log_n;
     args.log_lo = c->log_lo;
     args.log_hi = c->log_hi;

@@ -172,6 +172,47 @@ void ref_fwd_round(const int64_t* v8, const uint64_t* tw7, uint64_t q, uint64_t*
     }
 }
 
+// three inverse butterfly stages on eight reduced values (a round of the inverse transforms: sum re-centred, difference
+// times the twiddle), with the twiddle's quotient precomputed or with its value alone; returns the largest multiplicand seen
+static double inv_round(int64_t* v8, const uint64_t* tw7, uint64_t q, bool value_only) {
+    const double qd = (double)q, qinv = 1.0 / qd;
+    double v[8], worst = 0.0;
+    for (int j = 0; j < 8; j++) v[j] = (double)v8[j];
+    for (int a = 2; a >= 0; a--) {
+        const int half = 8 >> (a + 1);
+        for (int rr = 0; rr < 8; rr++) {
+            if (rr & half) continue;
+            const double w = (double)tw7[(1 << a) - 1 + (rr >> (3 - a))];
+            const double s = v[rr] + v[rr + half], d = v[rr] - v[rr + half];
+            if (__builtin_fabs(d) > worst) worst = __builtin_fabs(d);
+            v[rr] = f64m_reduce(s, qd, qinv);
+            v[rr + half] = value_only ? f64m_mulmod_any(d, w, qd, qinv) : f64m_mulmod(d, w, w / qd, qd);
+        }
+    }
+    for (int j = 0; j < 8; j++) v8[j] = as_int(v[j]);
+    return worst;
+}
+double run_inv_round(int64_t* v8, const uint64_t* tw7, uint64_t q) { return inv_round(v8, tw7, q, false); }
+double run_inv_round_any(int64_t* v8, const uint64_t* tw7, uint64_t q) { return inv_round(v8, tw7, q, true); }
+void ref_inv_round(const int64_t* v8, const uint64_t* tw7, uint64_t q, uint64_t* out8) {
+    i128 v[8];
+    for (int j = 0; j < 8; j++) v[j] = v8[j];
+    for (int a = 2; a >= 0; a--) {
+        const int half = 8 >> (a + 1);
+        for (int rr = 0; rr < 8; rr++) {
+            if (rr & half) continue;
+            const i128 s = v[rr] + v[rr + half], d = v[rr] - v[rr + half];
+            v[rr] = s % (i128)q;
+            v[rr + half] = d % (i128)q * (i128)tw7[(1 << a) - 1 + (rr >> (3 - a))] % (i128)q;
+        }
+    }
+    for (int j = 0; j < 8; j++) {
+        i128 m = v[j] % (i128)q;
+        if (m < 0) m += q;
+        out8[j] = (uint64_t)m;
+    }
+}
+
 // the fold of nd digit diagonals (rows of D: [n][nd] 32-bit signed; constants c[nd] < q), nd in {9, 10, 13}: the parts
 // of the constants and the multiplier 2^17 mod q are formed here the way the library's table holds them
 int run_fold(const int32_t* D, const uint64_t* c, uint32_t nd, uint64_t q, double* r, size_t n) {

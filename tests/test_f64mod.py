@@ -32,6 +32,8 @@ def build_checker(out_dir):
     lib.chk_fold.restype = ctypes.c_long
     lib.run_fwd_round.restype = ctypes.c_double
     lib.run_fwd_round_any.restype = ctypes.c_double
+    lib.run_inv_round.restype = ctypes.c_double
+    lib.run_inv_round_any.restype = ctypes.c_double
     return lib
 
 
@@ -254,6 +256,32 @@ def test_forward_round_of_three_stages(lib, q, fn):
         worst = max(worst, getattr(lib, fn)(ptr(got), ptr(tw), ctypes.c_uint64(q)))
         assert np.all(np.abs(got) <= half), (q, trial)
         assert np.array_equal(np.mod(got, q).astype(np.uint64), want), (q, trial)
+    assert worst < 2 * q
+
+
+@pytest.mark.parametrize("fn", ["run_inv_round", "run_inv_round_any"])
+@pytest.mark.parametrize("q", PRIMES[:5])
+def test_inverse_round_of_three_stages(lib, q, fn):
+    """Three inverse butterfly stages (sum re-centred, difference times the twiddle) chained as the inverse transforms chain
+    them, from reduced inputs and from inputs as large as a previous round's products leave them (below q): every
+    multiplicand stays below 2q, every value that enters the next round stays below q, the results match exact integer
+    butterflies.  With the twiddle's quotient precomputed, and with the twiddle's value alone (the inverse lo pass)."""
+    rng = np.random.default_rng(q % 1000003 + 6)
+    worst = 0.0
+    for bound in (q // 2 + 1, q - 1):
+        for trial in range(10000):
+            if trial < 64:
+                v = np.array([bound if (trial >> j) & 1 else -bound for j in range(6)] + [bound, -bound], dtype=np.int64)
+                tw = np.array([q - 1, 1, q - 1, (q + 1) // 2, (q - 1) // 2, q - 2, 2], dtype=np.uint64)
+            else:
+                v = rng.integers(-bound, bound + 1, size=8, dtype=np.int64)
+                tw = rng.integers(0, q, size=7, dtype=np.uint64)
+            want = np.empty(8, dtype=np.uint64)
+            lib.ref_inv_round(ptr(v), ptr(tw), ctypes.c_uint64(q), ptr(want))
+            got = v.copy()
+            worst = max(worst, getattr(lib, fn)(ptr(got), ptr(tw), ctypes.c_uint64(q)))
+            assert np.all(np.abs(got) < q), (q, trial)
+            assert np.array_equal(np.mod(got, q).astype(np.uint64), want), (q, trial)
     assert worst < 2 * q
 
 
