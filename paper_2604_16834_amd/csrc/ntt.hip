@@ -303,7 +303,8 @@ __device__ __forceinline__ void load_lo_tw(const PolyRef<A>& P, u32 T, typename 
 //   round C: thread = (d3, d2, d0),        points over d1          (distances 16, 8, 4)
 //   round D: thread = pos / 8,             8 consecutive points    (distances 2, 1)
 // A workgroup transforms the same (limb, block) slice of IT consecutive batch items one after the other: the
-// slice's twiddles (as many bytes as the tile itself) are fetched once for all of them, and the next item's
+// slice's twiddles (half as many bytes as the tile itself as values alone, as many with their quotients) are fetched once for
+// all of them, and the next item's
 // points are requested before the current item's butterflies start, so their latency hides behind a whole
 // tile of work.  A buffer is rewritten only after a barrier that every reader of its old contents has passed: the
 // forward pass has four exchanges per item (the last one turns each thread's 8 consecutive results into stores of
@@ -489,7 +490,7 @@ __device__ __forceinline__ void fwd_lo_body(const NttArgs& args, const PolyList&
 }
 
 // The plain forward lo pass with the workgroup's batch items in a loop: items tile.b, tile.b + (the grid's extent over
-// items), ... of the same 2^11-point slice.  The slice's 27 twiddle words per thread are 432 bytes against the 128 bytes of
+// items), ... of the same 2^11-point slice.  The slice's 27 twiddles per thread are 216 bytes (432 with their quotients) against the 128 bytes of
 // an item's points and results, so a workgroup that fetches them for two items still moves more twiddles than data through
 // the CU's cache; this one fetches them once for all its items and requests an item's points while the previous one is
 // transformed.  Same rounds, same LDS exchanges as fwd_lo_body.
@@ -614,7 +615,7 @@ __global__ __launch_bounds__(NTT_THREADS) void ntt_fwd_lo_mac_kernel(NttArgs arg
     const LoTile tile = lo_tile(args.log_hi, args.lo_group);
     const u32 blk = tile.blk, e = tile.a, m_idx = pl_at(pl.mod, e);
     // the batch items of this workgroup: tile.b, tile.b + (the grid's extent over items), ...: a workgroup that takes several
-    // fetches the slice's twiddles (as many bytes as an item's points) once for all of them and requests an item's first
+    // fetches the slice's twiddles (half as many bytes as an item's points) once for all of them and requests an item's first
     // points before it is done with the previous item
     const u32 b_step = args.lo_group ? gridDim.y : gridDim.x;
     const size_t N = (size_t)1 << args.log_n, off = (size_t)blk << 11;
