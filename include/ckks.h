@@ -329,8 +329,12 @@ int he_poly_act_deg7(const ckks_ctx* ctx, const uint64_t* const* h_d_x, uint32_t
  *   CKKS_F64_REDUCE      out = y - q*round(y/q)                              (d_w, d_wq unused)
  *   CKKS_F64_CANONICAL   out = y mod q in [0, q), through REDUCE             (d_w, d_wq unused)
  *   CKKS_F64_CENTRE      out = y*w mod q as the centred residue, through MULMOD
+ *   CKKS_F64_DOT8, _DOT9 out[i] = sum_a y[i][a] * w[a] mod q as a reduced double: the basis-conversion sum of 8 or 9 terms
+ *                        (d_y int64[n][8 or 9], centred residues |y| < 2^49; d_w uint64[8 or 9] in [0, q), taken by their
+ *                        centred representatives as the library's tables hold them; d_wq unused)
  * d_y int64[n] (integers, |y| < 2^51 for the products, < 2^53 otherwise), d_w uint64[n] in [0, q), d_out double[n]. */
-enum ckks_f64_op { CKKS_F64_MULMOD = 0, CKKS_F64_MULMOD_ANY = 1, CKKS_F64_REDUCE = 2, CKKS_F64_CANONICAL = 3, CKKS_F64_CENTRE = 4 };
+enum ckks_f64_op { CKKS_F64_MULMOD = 0, CKKS_F64_MULMOD_ANY = 1, CKKS_F64_REDUCE = 2, CKKS_F64_CANONICAL = 3, CKKS_F64_CENTRE = 4,
+                   CKKS_F64_DOT8 = 5, CKKS_F64_DOT9 = 6 };
 int ckks_f64mod_probe(int op, const int64_t* d_y, const uint64_t* d_w, const double* d_wq, uint64_t q, double* d_out, size_t n,
                       void* stream);
 

@@ -356,13 +356,17 @@ def he_conv_check_weights(ctx: Context, c_in: int, c_out: int, level: int, w_res
     ctx._check(_lib.he_conv_check_weights(ctx.handle, C.byref(d), _ptr(w_res), _stream(stream)))
 
 
-CKKS_F64_MULMOD, CKKS_F64_MULMOD_ANY, CKKS_F64_REDUCE, CKKS_F64_CANONICAL, CKKS_F64_CENTRE = range(5)
+CKKS_F64_MULMOD, CKKS_F64_MULMOD_ANY, CKKS_F64_REDUCE, CKKS_F64_CANONICAL, CKKS_F64_CENTRE, CKKS_F64_DOT8, CKKS_F64_DOT9 = range(7)
 
 
 def ckks_f64mod_probe(op: int, y: torch.Tensor, w: Optional[torch.Tensor], wq: Optional[torch.Tensor], q: int,
                       out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
-    """y int64[n], w int64[n] (uint64 residues bit for bit) or None, wq float64[n] or None -> float64[n]."""
-    n = y.numel()
+    """y int64[n], w int64[n] (uint64 residues bit for bit) or None, wq float64[n] or None -> float64[n]; the conversion sums
+    (CKKS_F64_DOT8, CKKS_F64_DOT9): y int64[n][8 or 9], w int64[8 or 9] -> float64[n]."""
+    nd = {CKKS_F64_DOT8: 8, CKKS_F64_DOT9: 9}.get(int(op))
+    if nd is not None and (y.dim() != 2 or y.shape[1] != nd or w is None or w.numel() != nd or not y.is_contiguous()):
+        raise CkksError(CKKS_ERR_INVALID_ARG, "ckks_f64mod_probe: a conversion sum takes y [n][%d] and %d constants" % (nd, nd))
+    n = y.shape[0] if nd is not None else y.numel()
     if out is None:
         out = torch.empty(n, dtype=torch.float64, device=y.device)
     rc = _lib.ckks_f64mod_probe(int(op), _ptr(y), _ptr(w) if w is not None else None, _ptr(wq) if wq is not None else None, int(q), _ptr(out), n,

@@ -49,6 +49,42 @@ def test_device_products_are_exact(lib, q):
 
 
 @pytest.mark.parametrize("q", PRIMES)
+def test_device_twiddle_products_up_to_2q(lib, q):
+    """The lo passes' butterflies take the quotient from the rounded product for multiplicands up to 2q: exact, at most q."""
+    rng = np.random.default_rng(q % 1000003 + 13)
+    y, w = cases(q, 2 * q, rng, 500_000)
+    r = hx.ckks_f64mod_probe(hx.CKKS_F64_MULMOD_ANY, dev(y), dev(w), None, q).cpu().numpy()
+    worst = ctypes.c_double(0)
+    bad = lib.chk_product(ptr(y), ptr(w), ptr(r), ctypes.c_uint64(q), ctypes.c_size_t(len(y)), 1, 1, ctypes.byref(worst))
+    assert bad < 0, f"q={q}: y={int(y[bad])} w={int(w[bad])} gave {r[bad]!r}"
+
+
+@pytest.mark.parametrize("nd,op", [(8, "CKKS_F64_DOT8"), (9, "CKKS_F64_DOT9")])
+@pytest.mark.parametrize("q", PRIMES)
+def test_device_conversion_sums(lib, q, nd, op):
+    """The basis-conversion sum as a chain of fused multiply-adds on the device: operands at their extremes in one sign and
+    alternating, products on the chain's rounding ties, random rows; against 128-bit integers."""
+    rng = np.random.default_rng(q % 1000003 + 14 + nd)
+    half_src = (1 << 49) - 1
+    n = 200_000
+    y = rng.integers(-half_src, half_src + 1, size=(n, nd), dtype=np.int64)
+    y[0], y[1] = half_src, -half_src
+    y[2, ::2], y[2, 1::2] = half_src, -half_src
+    y[3, ::2], y[3, 1::2] = -half_src, half_src
+    y[40:2000] = 4 * rng.integers(-(half_src // 4), half_src // 4, size=(1960, nd), dtype=np.int64) + 2
+    tie = min(1 << 48, 1 << (q.bit_length() - 2))
+    mixed = rng.integers(0, q, size=nd, dtype=np.uint64)
+    mixed[::2] = (q + 1) // 2
+    for cw in (rng.integers(0, q, size=nd, dtype=np.uint64), np.full(nd, q - 1, dtype=np.uint64), np.full(nd, (q + 1) // 2, dtype=np.uint64),
+               np.full(nd, (q - 1) // 2, dtype=np.uint64), np.full(nd, tie, dtype=np.uint64), mixed):
+        cw = np.ascontiguousarray(cw)
+        yy = np.ascontiguousarray(y)
+        r = hx.ckks_f64mod_probe(getattr(hx, op), dev(yy), dev(cw), None, q).cpu().numpy()
+        bad = lib.chk_dot(ptr(yy), ptr(cw), nd, ptr(r), ctypes.c_uint64(q), ctypes.c_size_t(n))
+        assert bad < 0, f"q={q} nd={nd}: row {yy[bad].tolist()} gave {r[bad]!r}"
+
+
+@pytest.mark.parametrize("q", PRIMES)
 def test_device_reduce_canonical_and_centre(lib, q):
     rng = np.random.default_rng(q % 1000003 + 12)
     lim = 1 << 53
