@@ -1194,10 +1194,13 @@ static void launch_inv_lo(u32 items, dim3 grid, hipStream_t st, const NttArgs& a
     else launch_inv_lo_it<A, 1>(grid, st, args, pl, mul);
 }
 
-constexpr u32 CONV_TARGETS = 4;  // target limbs per workgroup of the converting hi pass
-template <int LOG_HI>
+// Target limbs per workgroup of the converting hi pass: four, or six where there are many of them and the ring is large (the
+// source residues are fetched by four workgroups instead of six for 24 targets; the pass takes as long by itself and leaves
+// more of the chip to the other stream's kernels: 0.5 ms per step of the block slice; with few targets or small launches the
+// larger groups cost parallelism)
+static u32 conv_targets(u32 log_hi, u32 n_targets) { return (log_hi >= 4 && n_targets >= 12) ? 6 : 4; }
+template <int LOG_HI, int T>
 static void launch_hi_conv_ap(u32 ap, dim3 grid, hipStream_t st, const NttArgs& args, const PolyList& pl, const ConvPrologue& cp) {
-    constexpr int T = CONV_TARGETS;
     if (ap == 4 && cp.nd == 1)  // the rescale: one dropped limb
         hipLaunchKernelGGL((ntt_fwd_hi_conv_kernel<LOG_HI, 4, T, 1>), grid, dim3(NTT_THREADS), 0, st, args, pl, cp);
     else if (ap == 4) hipLaunchKernelGGL((ntt_fwd_hi_conv_kernel<LOG_HI, 4, T>), grid, dim3(NTT_THREADS), 0, st, args, pl, cp);
@@ -1208,13 +1211,14 @@ static void launch_hi_conv_ap(u32 ap, dim3 grid, hipStream_t st, const NttArgs& 
     else hipLaunchKernelGGL((ntt_fwd_hi_conv_kernel<LOG_HI, 16, T>), grid, dim3(NTT_THREADS), 0, st, args, pl, cp);
 }
 static void launch_hi_conv(u32 log_hi, u32 ap, dim3 grid, hipStream_t st, const NttArgs& args, const PolyList& pl, const ConvPrologue& cp) {
+    const bool six = conv_targets(log_hi, pl.n) == 6;
     switch (log_hi) {
-        case 1: launch_hi_conv_ap<1>(ap, grid, st, args, pl, cp); break;
-        case 2: launch_hi_conv_ap<2>(ap, grid, st, args, pl, cp); break;
-        case 3: launch_hi_conv_ap<3>(ap, grid, st, args, pl, cp); break;
-        case 4: launch_hi_conv_ap<4>(ap, grid, st, args, pl, cp); break;
-        case 5: launch_hi_conv_ap<5>(ap, grid, st, args, pl, cp); break;
-        default: launch_hi_conv_ap<6>(ap, grid, st, args, pl, cp); break;
+        case 1: launch_hi_conv_ap<1, 4>(ap, grid, st, args, pl, cp); break;
+        case 2: launch_hi_conv_ap<2, 4>(ap, grid, st, args, pl, cp); break;
+        case 3: launch_hi_conv_ap<3, 4>(ap, grid, st, args, pl, cp); break;
+        case 4: six ? launch_hi_conv_ap<4, 6>(ap, grid, st, args, pl, cp) : launch_hi_conv_ap<4, 4>(ap, grid, st, args, pl, cp); break;
+        case 5: six ? launch_hi_conv_ap<5, 6>(ap, grid, st, args, pl, cp) : launch_hi_conv_ap<5, 4>(ap, grid, st, args, pl, cp); break;
+        default: six ? launch_hi_conv_ap<6, 6>(ap, grid, st, args, pl, cp) : launch_hi_conv_ap<6, 4>(ap, grid, st, args, pl, cp); break;
     }
 }
 
@@ -1307,7 +1311,8 @@ static hipError_t launch_ntt_any(const ckks_ctx* c, bool inverse, const u64* src
             args.last = 0;
             if (conv) {  // reads the digit's nd limbs for every target limb (from cache after the first), writes the target limbs
                 ProfScope ps__(c, K_NTT_FWD_HI, st, 8.0 * c->N * batch * ((double)conv->nd + pl.n), hi_ops);
-                launch_hi_conv(c->log_hi, conv->ap, dim3(grid.x, (pl.n + CONV_TARGETS - 1) / CONV_TARGETS * batch), st, args, pl, *conv);
+                const u32 ct = conv_targets(c->log_hi, pl.n);
+                launch_hi_conv(c->log_hi, conv->ap, dim3(grid.x, (pl.n + ct - 1) / ct * batch), st, args, pl, *conv);
             } else {
                 ProfScope ps__(c, K_NTT_FWD_HI, st, pass_bytes, hi_ops);
                 hi(args, pl);
