@@ -1198,7 +1198,8 @@ static void launch_inv_lo(u32 items, dim3 grid, hipStream_t st, const NttArgs& a
 // source residues are fetched by four workgroups instead of six for 24 targets; the pass takes as long by itself and leaves
 // more of the chip to the other stream's kernels: 0.5 ms per step of the block slice; with few targets or small launches the
 // larger groups cost parallelism)
-static u32 conv_targets(u32 log_hi, u32 n_targets) { return (log_hi >= 4 && n_targets >= 12) ? 6 : 4; }
+// (not for the one-term "conversion" of the rescale, which has no arithmetic to share: 36 us with four, 41 with six)
+static u32 conv_targets(u32 log_hi, u32 n_targets, u32 nd) { return (log_hi >= 4 && n_targets >= 12 && nd > 1) ? 6 : 4; }
 template <int LOG_HI, int T>
 static void launch_hi_conv_ap(u32 ap, dim3 grid, hipStream_t st, const NttArgs& args, const PolyList& pl, const ConvPrologue& cp) {
     if (ap == 4 && cp.nd == 1)  // the rescale: one dropped limb
@@ -1211,7 +1212,7 @@ static void launch_hi_conv_ap(u32 ap, dim3 grid, hipStream_t st, const NttArgs& 
     else hipLaunchKernelGGL((ntt_fwd_hi_conv_kernel<LOG_HI, 16, T>), grid, dim3(NTT_THREADS), 0, st, args, pl, cp);
 }
 static void launch_hi_conv(u32 log_hi, u32 ap, dim3 grid, hipStream_t st, const NttArgs& args, const PolyList& pl, const ConvPrologue& cp) {
-    const bool six = conv_targets(log_hi, pl.n) == 6;
+    const bool six = conv_targets(log_hi, pl.n, cp.nd) == 6;
     switch (log_hi) {
         case 1: launch_hi_conv_ap<1, 4>(ap, grid, st, args, pl, cp); break;
         case 2: launch_hi_conv_ap<2, 4>(ap, grid, st, args, pl, cp); break;
@@ -1311,7 +1312,7 @@ static hipError_t launch_ntt_any(const ckks_ctx* c, bool inverse, const u64* src
             args.last = 0;
             if (conv) {  // reads the digit's nd limbs for every target limb (from cache after the first), writes the target limbs
                 ProfScope ps__(c, K_NTT_FWD_HI, st, 8.0 * c->N * batch * ((double)conv->nd + pl.n), hi_ops);
-                const u32 ct = conv_targets(c->log_hi, pl.n);
+                const u32 ct = conv_targets(c->log_hi, pl.n, conv->nd);
                 launch_hi_conv(c->log_hi, conv->ap, dim3(grid.x, (pl.n + ct - 1) / ct * batch), st, args, pl, *conv);
             } else {
                 ProfScope ps__(c, K_NTT_FWD_HI, st, pass_bytes, hi_ops);
