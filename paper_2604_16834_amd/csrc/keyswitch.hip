@@ -405,12 +405,17 @@ __global__ __launch_bounds__(KS_THREADS) void mask_keys_kernel(TapSet T, u64* __
 }
 
 // SMALL: every modulus below 2^50 (carry-free 25-bit-split accumulation, three multiply-adds per product).
-template <int BETA, bool SMALL>
+// F64 (with SMALL, mcf given): the sums of BETA + 1 products as chains of fused multiply-adds on centred doubles (f64m_dot_w:
+// four full-rate operations per term where the split integer sum takes three quarter-rate 64-bit multiply-adds and the
+// splits); the digits and the ciphertext's words are centred once per thread, a tap's key words once per tap.
+template <int BETA, bool SMALL, bool F64 = false>
 __global__ __launch_bounds__(KS_THREADS) void key_inner_taps_kernel(DigitSrc digits, TapSet T,
                                                                     const u64* __restrict__ mk, const u64* __restrict__ mp,
                                                                     PtrList8 c0s, u64* __restrict__ xs, XLayout xl, u32 k0base,
                                                                     u32 k_bstride, const ModConst* __restrict__ mc, u32 log_n,
-                                                                    u32 level, u32 num_q, u32 E, u32 n, u32 M, const u64* __restrict__ negp) {
+                                                                    u32 level, u32 num_q, u32 E, u32 n, u32 M, const u64* __restrict__ negp,
+                                                                    const ModConstF* __restrict__ mcf) {
+    static_assert(!F64 || SMALL, "the double-precision sums need moduli below 2^50");
     // negp != nullptr: no masks; the keys are read where they are (T.key[i]: [dnum][2][M][N]) and mask * P is P itself
     const u32 N = 1u << log_n;
     const u32 xsrc = blockIdx.x * KS_THREADS + threadIdx.x;
@@ -429,6 +434,21 @@ __global__ __launch_bounds__(KS_THREADS) void key_inner_taps_kernel(DigitSrc dig
 #pragma unroll
         for (u32 j = 0; j < BETA; j++) dv[b][j] = on ? digit_row(digits, b, j, e, E, N, level)[xsrc] : 0;
     }
+    // F64: the centred representative of a residue as a double
+    const double qd = F64 ? mcf[t].q : 0.0, qinv = F64 ? mcf[t].qinv : 0.0, halfq = 0.5 * qd;
+    auto centred = [&](u64 v) {
+        const double d = f64m_from_u64(v);
+        return d > halfq ? d - qd : d;
+    };
+    double yd[CT_BATCH][BETA + 1];  // F64: digits and the ciphertext's word of every batch item
+    if (F64) {
+#pragma unroll
+        for (u32 b = 0; b < CT_BATCH; b++) {
+#pragma unroll
+            for (u32 j = 0; j < BETA; j++) yd[b][j] = centred(dv[b][j]);
+            yd[b][BETA] = centred(cv[b]);
+        }
+    }
     for (u32 i = 0; i < T.n_taps; i++) {
         const u32 x = galois_gather_index(xsrc, T.ginv[i], log_n);  // destination point
         u64 k0[BETA], k1[BETA];
@@ -440,7 +460,20 @@ __global__ __launch_bounds__(KS_THREADS) void key_inner_taps_kernel(DigitSrc dig
         }
         const u64 kp = direct ? pres : (has_add ? mp[((size_t)i * (level + 1) + e) * N + x] : 0);
         u64* ot = xs + xl.at(k0base + T.tap[i], 0, e, x);
-        if (SMALL) {
+        if (F64) {
+            double w0[BETA + 1], w1[BETA];
+#pragma unroll
+            for (u32 j = 0; j < BETA; j++) { w0[j] = centred(k0[j]); w1[j] = centred(k1[j]); }
+            w0[BETA] = centred(kp);  // zero on the special primes
+#pragma unroll
+            for (u32 b = 0; b < CT_BATCH; b++) {
+                if (b < n) {
+                    u64* ob = ot + (size_t)b * k_bstride * xl.s_k;
+                    ob[0] = f64m_canonical(f64m_dot_w<BETA + 1>(yd[b], w0, qd, qinv), qd);
+                    ob[xl.s_comp] = f64m_canonical(f64m_dot_w<BETA>(yd[b], w1, qd, qinv), qd);
+                }
+            }
+        } else if (SMALL) {
             Split50 s0[BETA], s1[BETA];
 #pragma unroll
             for (u32 j = 0; j < BETA; j++) { s0[j] = split50(k0[j]); s1[j] = split50(k1[j]); }
@@ -555,12 +588,15 @@ hipError_t launch_key_inner_taps(const ckks_ctx* c, u32 level, const DigitSrc& d
                    2.0 * n_taps * n * c->N * E * (beta + 1.0));
 #define KI_TAPS(B_)                                                                                                                  \
     do {                                                                                                                             \
-        if (c->small_q)                                                                                                              \
+        if (c->small_q && c->d_mcf)                                                                                                  \
+            hipLaunchKernelGGL((key_inner_taps_kernel<B_, true, true>), grid, dim3(KS_THREADS), 0, st, digits, T, mk, mp, cl, xs, xl, \
+                               k0, k_bstride, c->d_mc, c->log_n, level, c->num_q, E, n, c->M, negp_direct, c->d_mcf);                \
+        else if (c->small_q)                                                                                                         \
             hipLaunchKernelGGL((key_inner_taps_kernel<B_, true>), grid, dim3(KS_THREADS), 0, st, digits, T, mk, mp, cl, xs, xl, \
-                               k0, k_bstride, c->d_mc, c->log_n, level, c->num_q, E, n, c->M, negp_direct);                          \
+                               k0, k_bstride, c->d_mc, c->log_n, level, c->num_q, E, n, c->M, negp_direct, c->d_mcf);                \
         else                                                                                                                         \
             hipLaunchKernelGGL((key_inner_taps_kernel<B_, false>), grid, dim3(KS_THREADS), 0, st, digits, T, mk, mp, cl, xs, xl, \
-                               k0, k_bstride, c->d_mc, c->log_n, level, c->num_q, E, n, c->M, negp_direct);                          \
+                               k0, k_bstride, c->d_mc, c->log_n, level, c->num_q, E, n, c->M, negp_direct, c->d_mcf);                \
     } while (0)
     if (beta == 1) KI_TAPS(1);
     else if (beta == 2) KI_TAPS(2);
