@@ -138,8 +138,9 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
     std::vector<TwPair> tw, itw;
     std::vector<TwF> twf, itwf;
     std::vector<ModConstF> mcf;
-    if (c->ntt_f64) { twf.resize((size_t)M * N); itwf.resize((size_t)M * N); mcf.resize(M); }
+    if (c->ntt_f64) { twf.resize((size_t)M * N); itwf.resize((size_t)M * N); }
     else { tw.resize((size_t)M * N); itw.resize((size_t)M * N); }
+    if (c->small_q) mcf.resize(M);  // also read by the kernels that are double-precision at any ring size (inner products, matrix-core sum)
     for (u32 t = 0; t < M; t++) {
         const u64 q = c->mod[t];
         ModConst& m = c->mc[t];
@@ -149,7 +150,7 @@ extern "C" int ckks_ctx_create(const ckks_params* p, ckks_ctx** out) {
         m.pad = 0;
         m.n_inv = h_invmod(N % q, q);
         m.n_inv_sh = h_shoup(m.n_inv, q);
-        if (c->ntt_f64) {  // every value below is an integer below 2^50: exact as a double; the quotients are correctly rounded
+        if (c->small_q) {  // every value below is an integer below 2^50: exact as a double; the quotients are correctly rounded
             mcf[t].q = (double)q;
             mcf[t].qinv = 1.0 / (double)q;
             mcf[t].ninv = (double)m.n_inv;

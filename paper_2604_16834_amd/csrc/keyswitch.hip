@@ -404,18 +404,17 @@ __global__ __launch_bounds__(KS_THREADS) void mask_keys_kernel(TapSet T, u64* __
     if (e <= level) mp[((size_t)i * (level + 1) + e) * N + x] = mulmod_barrett(mv, m.q - negp[e], m);
 }
 
-// SMALL: every modulus below 2^50 (carry-free 25-bit-split accumulation, three multiply-adds per product).
-// F64 (with SMALL, mcf given): the sums of BETA + 1 products as chains of fused multiply-adds on centred doubles (f64m_dot_w:
-// four full-rate operations per term where the split integer sum takes three quarter-rate 64-bit multiply-adds and the
-// splits); the digits and the ciphertext's words are centred once per thread, a tap's key words once per tap.
-template <int BETA, bool SMALL, bool F64 = false>
+// F64: every modulus below 2^50: the sums of BETA + 1 products as chains of fused multiply-adds on centred doubles (f64m_dot_w:
+// four full-rate operations per term where a split integer sum takes three quarter-rate 64-bit multiply-adds and the splits:
+// 117 registers instead of 232, 776 us instead of 904 for eight ciphertexts and nine taps at N = 2^16); the digits and the
+// ciphertext's words are centred once per thread, a tap's key words once per tap.  Otherwise 128-bit integer sums.
+template <int BETA, bool F64>
 __global__ __launch_bounds__(KS_THREADS) void key_inner_taps_kernel(DigitSrc digits, TapSet T,
                                                                     const u64* __restrict__ mk, const u64* __restrict__ mp,
                                                                     PtrList8 c0s, u64* __restrict__ xs, XLayout xl, u32 k0base,
                                                                     u32 k_bstride, const ModConst* __restrict__ mc, u32 log_n,
                                                                     u32 level, u32 num_q, u32 E, u32 n, u32 M, const u64* __restrict__ negp,
                                                                     const ModConstF* __restrict__ mcf) {
-    static_assert(!F64 || SMALL, "the double-precision sums need moduli below 2^50");
     // negp != nullptr: no masks; the keys are read where they are (T.key[i]: [dnum][2][M][N]) and mask * P is P itself
     const u32 N = 1u << log_n;
     const u32 xsrc = blockIdx.x * KS_THREADS + threadIdx.x;
@@ -471,27 +470,6 @@ __global__ __launch_bounds__(KS_THREADS) void key_inner_taps_kernel(DigitSrc dig
                     u64* ob = ot + (size_t)b * k_bstride * xl.s_k;
                     ob[0] = f64m_canonical(f64m_dot_w<BETA + 1>(yd[b], w0, qd, qinv), qd);
                     ob[xl.s_comp] = f64m_canonical(f64m_dot_w<BETA>(yd[b], w1, qd, qinv), qd);
-                }
-            }
-        } else if (SMALL) {
-            Split50 s0[BETA], s1[BETA];
-#pragma unroll
-            for (u32 j = 0; j < BETA; j++) { s0[j] = split50(k0[j]); s1[j] = split50(k1[j]); }
-            const Split50 sp = split50(kp);
-#pragma unroll
-            for (u32 b = 0; b < CT_BATCH; b++) {
-                if (b < n) {
-                    Acc50 a0 = {0, 0, 0}, a1 = {0, 0, 0};
-#pragma unroll
-                    for (u32 j = 0; j < BETA; j++) {
-                        const Split50 d = split50(dv[b][j]);
-                        acc50_mad(a0, d, s0[j]);
-                        acc50_mad(a1, d, s1[j]);
-                    }
-                    acc50_mad(a0, split50(cv[b]), sp);
-                    u64* ob = ot + (size_t)b * k_bstride * xl.s_k;
-                    ob[0] = barrett_reduce(acc50_value(a0), m);
-                    ob[xl.s_comp] = barrett_reduce(acc50_value(a1), m);
                 }
             }
         } else {
@@ -588,10 +566,7 @@ hipError_t launch_key_inner_taps(const ckks_ctx* c, u32 level, const DigitSrc& d
                    2.0 * n_taps * n * c->N * E * (beta + 1.0));
 #define KI_TAPS(B_)                                                                                                                  \
     do {                                                                                                                             \
-        if (c->small_q && c->d_mcf)                                                                                                  \
-            hipLaunchKernelGGL((key_inner_taps_kernel<B_, true, true>), grid, dim3(KS_THREADS), 0, st, digits, T, mk, mp, cl, xs, xl, \
-                               k0, k_bstride, c->d_mc, c->log_n, level, c->num_q, E, n, c->M, negp_direct, c->d_mcf);                \
-        else if (c->small_q)                                                                                                         \
+        if (c->small_q)                                                                                                              \
             hipLaunchKernelGGL((key_inner_taps_kernel<B_, true>), grid, dim3(KS_THREADS), 0, st, digits, T, mk, mp, cl, xs, xl, \
                                k0, k_bstride, c->d_mc, c->log_n, level, c->num_q, E, n, c->M, negp_direct, c->d_mcf);                \
         else                                                                                                                         \

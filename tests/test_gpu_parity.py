@@ -236,7 +236,7 @@ def conv_case(name, level=None, bits=50, four_keys=False, deferred=False, merged
 
 @pytest.mark.parametrize("name,level,bits", [("cfg1_single_conv", None, 50), ("cfg1_single_conv_k1", None, 50), ("small_conv", None, 50),
                                              ("small_conv", 2, 50), ("small_conv", None, 56), ("small_conv", None, 36),
-                                             ("small_conv_d6", None, 50)])
+                                             ("small_conv_d6", None, 50), ("tiny_ring_conv", None, 50)])
 def test_he_conv_matches_oracle_and_float_conv(name, level, bits):
     # 56-bit primes take the general 128-bit accumulation kernels, <= 50-bit ones the carry-free split ones
     wl, p, orc, level, s_ntt, img, w, scale, cts, keys, masks, w_int, outs = conv_case(name, level, bits)
@@ -292,7 +292,8 @@ def test_he_conv_deferred_moddown_matches_oracle(name, level, bits):
 
 
 @pytest.mark.parametrize("name,level,bits", [("cfg1_single_conv", None, 50), ("small_conv", None, 50), ("small_conv", 1, 50),
-                                             ("small_conv", 3, 56), ("small_conv_d6", None, 50), ("small_conv_d6", 3, 50)])
+                                             ("small_conv", 3, 56), ("small_conv_d6", None, 50), ("small_conv_d6", 3, 50),
+                                             ("tiny_ring_conv", None, 50)])
 def test_he_conv_deferred_merged_division_matches_oracle(name, level, bits):
     """The deferred schedule with ModDown and rescale of every sum as one division by P*q_level."""
     wl, p, orc, level, s_ntt, img, w, scale, cts, keys, masks, w_int, outs = conv_case(name, level, bits, deferred=True, merged=True)

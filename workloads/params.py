@@ -145,6 +145,8 @@ CONFIGS: Dict[str, Workload] = {
     # 64 input channels (9 * 64 = 576 terms, a whole number of 64-term blocks) and 40 outputs (both 32-channel output tiles live):
     # the instantiation of the multiply-accumulate that the block-slice benchmark runs, at a size the oracle affords
     "small_conv_c64": Workload("small_conv_c64", 12, 4, 2, 2, 8, 8, 32, 64, 40),
+    # a ring below the transforms' tile size (N = 2^10: single-kernel transforms, stand-alone conversions) with 50-bit primes
+    "tiny_ring_conv": Workload("tiny_ring_conv", 10, 4, 2, 2, 8, 8, 8, 2, 2),
     # six one-limb digits: more than the fused multi-rotation launches take (the one-launch-per-tap paths)
     "small_conv_d6": Workload("small_conv_d6", 12, 6, 2, 6, 8, 8, 32, 3, 2),
 }
