@@ -210,9 +210,13 @@ hipError_t launch_key_inner(const ckks_ctx* c, u32 level, const DigitSrc& digits
 // rotation and relinearisation keys): every thread keeps its key words while it walks the batch, so
 // the key streams from HBM once per batch instead of once per key switch.
 // digits + b*digits_bstride: [beta][E][N];  v + b*v_bstride: [2][E][N]
+// F64 (every modulus below 2^50, at most four digits): the sums as chains of fused multiply-adds on centred doubles
+// (f64m_dot_w), as in the fused taps.
+template <bool F64>
 __global__ __launch_bounds__(KS_THREADS) void key_inner_multi_kernel(DigitSrc digits, const u64* __restrict__ key, u64* __restrict__ v,
                                                                      size_t v_bstride, const ModConst* __restrict__ mc, u32 log_n,
-                                                                     u32 level, u32 num_q, u32 M, u32 E, u32 beta, u32 g, u32 n) {
+                                                                     u32 level, u32 num_q, u32 M, u32 E, u32 beta, u32 g, u32 n,
+                                                                     const ModConstF* __restrict__ mcf) {
     const u32 N = 1u << log_n;
     const u32 x = blockIdx.x * KS_THREADS + threadIdx.x;
     if (x >= N) return;
@@ -220,6 +224,28 @@ __global__ __launch_bounds__(KS_THREADS) void key_inner_multi_kernel(DigitSrc di
     const u32 t = e <= level ? e : num_q + (e - level - 1);
     const u32 xs = g == 1 ? x : galois_gather_index(x, g, log_n);
     const ModConst m = mc[t];
+    if constexpr (F64) {  // beta <= 4: entries past the last digit are zero on both sides
+        const double qd = mcf[t].q, qinv = mcf[t].qinv, halfq = 0.5 * qd;
+        auto centred = [&](u64 w) {
+            const double d = f64m_from_u64(w);
+            return d > halfq ? d - qd : d;
+        };
+        double w0[4], w1[4];
+#pragma unroll
+        for (u32 j = 0; j < 4; j++) {
+            w0[j] = j < beta ? centred(key[(((size_t)j * 2 + 0) * M + t) * N + x]) : 0.0;
+            w1[j] = j < beta ? centred(key[(((size_t)j * 2 + 1) * M + t) * N + x]) : 0.0;
+        }
+        for (u32 b = 0; b < n; b++) {
+            double y[4];
+#pragma unroll
+            for (u32 j = 0; j < 4; j++) y[j] = j < beta ? centred(digit_row(digits, b, j, e, E, N, level)[xs]) : 0.0;
+            u64* vb = v + b * v_bstride;
+            vb[((size_t)0 * E + e) * N + x] = f64m_canonical(f64m_dot_w<4>(y, w0, qd, qinv), qd);
+            vb[((size_t)1 * E + e) * N + x] = f64m_canonical(f64m_dot_w<4>(y, w1, qd, qinv), qd);
+        }
+        return;
+    }
     if (beta <= 4) {
         // the thread's key words stay in registers for the whole batch
         u64 k0[4], k1[4];
@@ -264,8 +290,12 @@ hipError_t launch_key_inner_multi(const ckks_ctx* c, u32 level, const DigitSrc& 
     const u32 E = c->ext_limbs(level), beta = c->live_digits(level);
     dim3 grid((c->N + KS_THREADS - 1) / KS_THREADS, E);
     ProfScope ps__(c, K_KEY_INNER, st, 8.0 * c->N * E * (2.0 * beta + n * (beta + 2.0)), 2.0 * n * c->N * E * beta);
-    hipLaunchKernelGGL(key_inner_multi_kernel, grid, dim3(KS_THREADS), 0, st, digits, key, v, v_bstride, c->d_mc,
-                       c->log_n, level, c->num_q, c->M, E, beta, g, n);
+    if (c->small_q && beta <= 4)
+        hipLaunchKernelGGL(key_inner_multi_kernel<true>, grid, dim3(KS_THREADS), 0, st, digits, key, v, v_bstride, c->d_mc,
+                           c->log_n, level, c->num_q, c->M, E, beta, g, n, c->d_mcf);
+    else
+        hipLaunchKernelGGL(key_inner_multi_kernel<false>, grid, dim3(KS_THREADS), 0, st, digits, key, v, v_bstride, c->d_mc,
+                           c->log_n, level, c->num_q, c->M, E, beta, g, n, c->d_mcf);
     return hipGetLastError();
 }
 
