@@ -174,10 +174,11 @@ def test_ctct_mul_relin_matches_oracle(ks_setup, level):
 
 @pytest.mark.parametrize("log_n,num_q,num_p,dnum,bits", [(12, 8, 2, 4, 50), (12, 6, 3, 2, 50), (12, 5, 5, 1, 50), (13, 9, 3, 3, 50),
                                                        (12, 8, 2, 4, 56), (11, 6, 3, 2, 50), (12, 6, 2, 6, 50),
-                                                       (14, 4, 2, 2, 50), (15, 3, 2, 2, 50)])
+                                                       (14, 4, 2, 2, 50), (15, 3, 2, 2, 50), (15, 16, 4, 4, 50)])
 def test_key_switch_paths_with_other_digit_shapes(log_n, num_q, num_p, dnum, bits):
     """Four digits of two limbs, two of three, a single digit, three full digits of three, six digits of one limb (more digits
-    than the shared multi-rotation launch takes); rings with one to four first-pass stages and the single-pass ring; both
+    than the shared multi-rotation launch takes), four digits of four limbs at N = 2^15 (16 target limbs: the converting first
+    pass' groups of six with a ragged last group); rings with one to four first-pass stages and the single-pass ring; both
     arithmetic paths: key switch, relinearised product and both rotation modes at the
     top level, at a level with a ragged last digit and at level 0."""
     p = make_params(log_n, num_q, num_p, dnum, bits=bits)
